@@ -1,0 +1,261 @@
+"""CPU oracle for the Routing Mamba (RoM) layer forward pass and recurrent step.
+
+TEST INFRASTRUCTURE ONLY.  This is a plain, slow, fp64 statement of what the
+layer computes, written from the paper's equations.  Only tests, the smoke
+check and the benchmark's cpu_baseline leg may import it; the product path
+(the HIP library and its Python binding) never does, and shares no code with it.
+
+Every function upcasts its inputs to float64 and never rounds an intermediate.
+There is no token permutation, no tiling and no fusion: routed projections are
+the indicator sums of Eq. (10)/(11) evaluated expert by expert, the scan is the
+per-step recurrence of Eq. (5).
+
+Notation (paper Sec. 3.1 / Sec. 4): N tokens, D_m = d_model, D_e = d_inner,
+D_s = d_state, k = d_conv, R = dt_rank, E experts, K = top-K.
+
+Readings of the paper taken here (each is also listed in the design notes):
+  * gate_mode 0 is Eq. (9) as printed (softmax over all experts, masked to the
+    top-K); gate_mode 1 renormalises over the selected K (text before Eq. (9)).
+  * Eq. (10)/(11): the routed in/gate projections are *unweighted* sums over
+    the selected experts; only the out projection is gate-weighted (Eq. (12)).
+  * Eq. (6)/(13): (Y * SiLU-gate) is formed first, then multiplied by W_out.
+  * The discretised input matrix is the first-order form dt*B (not the exact
+    zero-order hold printed after Eq. (4)); A-bar = exp(dt*A) is exact.
+  * y gets the D*u skip term, dt = softplus(dt_proj(...) + dt_bias), the conv
+    has a bias: the standard Mamba layer the paper builds on (Sec. 3.1).
+  * Routed x/dt projections (the "Conv, Gate, dt, x, Out" variant of Table 1)
+    are indicator sums like Eq. (11); dt_bias is one shared vector.
+  * Top-K picks on logits, descending, lowest expert index on ties.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------
+# Router: Eq. (9)
+# --------------------------------------------------------------------------
+def router_logits(x, w_router, b_router=None):
+    """l[n, e] = sum_d x[n, d] * W_r[e, d] (+ b_r[e]).  x [N, D_m], w_router [E, D_m]."""
+    logits = np.asarray(x, F64) @ np.asarray(w_router, F64).T
+    if b_router is not None:
+        logits = logits + np.asarray(b_router, F64)[None, :]
+    return logits
+
+
+def topk_select(logits, top_k):
+    """K rounds of arg-max over the experts not yet chosen; ties go to the lowest index.
+
+    Returns idx [N, K] int32 with column k the (k+1)-th largest logit.
+    """
+    work = np.array(logits, F64, copy=True)
+    n = work.shape[0]
+    idx = np.empty((n, top_k), np.int32)
+    rows = np.arange(n)
+    for k in range(top_k):
+        best = np.argmax(work, axis=1)          # first occurrence = lowest index
+        idx[:, k] = best
+        work[rows, best] = -np.inf
+    return idx
+
+
+def topk_margin(logits, top_k):
+    """Smallest gap between consecutive sorted logits over ranks 1..K+1 (K if K == E).
+
+    A token whose margin is tiny may legitimately be routed differently by an
+    fp32 router; parity tests exclude such tokens from the exact-index check.
+    """
+    s = -np.sort(-np.asarray(logits, F64), axis=1)
+    hi = min(top_k + 1, s.shape[1])
+    if hi < 2:
+        return np.full(s.shape[0], np.inf)
+    return np.min(s[:, : hi - 1] - s[:, 1:hi], axis=1)
+
+
+def softmax(logits):
+    z = np.asarray(logits, F64)
+    z = z - z.max(axis=1, keepdims=True)
+    e = np.exp(z)
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def gate_weights(logits, idx, gate_mode):
+    """R_i of Eq. (9) for the selected experts: gate[n, k] = P[n, idx[n, k]] (mode 0),
+    divided by the sum over the K selected (mode 1)."""
+    p = softmax(logits)
+    g = np.take_along_axis(p, idx.astype(np.int64), axis=1)
+    if gate_mode == 1:
+        g = g / g.sum(axis=1, keepdims=True)
+    elif gate_mode != 0:
+        raise ValueError("gate_mode must be 0 or 1")
+    return g
+
+
+def expert_permutation(idx, n_experts):
+    """Grouping of the N*K (token, k) slots by expert, stable in slot order.
+
+    slot s = n*K + k.  counts[e] = number of slots routed to e; offsets = exclusive
+    prefix sum (offsets[E] = N*K); inv_perm[s] = offsets[e_s] + rank of s among the
+    slots of the same expert in ascending s; perm = inverse of inv_perm.
+    """
+    flat = np.asarray(idx, np.int64).reshape(-1)
+    counts = np.zeros(n_experts, np.int32)
+    for e in flat:
+        counts[e] += 1
+    offsets = np.zeros(n_experts + 1, np.int32)
+    for e in range(n_experts):
+        offsets[e + 1] = offsets[e] + counts[e]
+    cursor = offsets[:-1].astype(np.int64).copy()
+    inv_perm = np.empty(flat.size, np.int32)
+    perm = np.empty(flat.size, np.int32)
+    for s, e in enumerate(flat):
+        pos = cursor[e]
+        cursor[e] += 1
+        inv_perm[s] = pos
+        perm[pos] = s
+    return counts, offsets, perm, inv_perm
+
+
+# --------------------------------------------------------------------------
+# Routed projections: Eq. (10), (11), (13)
+# --------------------------------------------------------------------------
+def routed_linear(inp, w, idx):
+    """out[n, :] = sum_i 1[i in idx[n, :]] * inp[n, :] @ w[i].T     (Eq. (11) pattern)
+
+    inp [N, D_in], w [E, D_out, D_in], idx [N, K].  With E == 1 (shared module)
+    every token uses w[0] once.
+    """
+    inp = np.asarray(inp, F64)
+    n_exp = w.shape[0]
+    out = np.zeros((inp.shape[0], w.shape[1]), F64)
+    if n_exp == 1:
+        return inp @ np.asarray(w[0], F64).T
+    for i in range(n_exp):
+        rows = np.nonzero((idx == i).any(axis=1))[0]
+        if rows.size:
+            out[rows] += inp[rows] @ np.asarray(w[i], F64).T
+    return out
+
+
+def silu(v):
+    return v / (1.0 + np.exp(-v))
+
+
+def softplus(v):
+    # log(1 + exp(v)), written so that large |v| neither overflows nor loses digits
+    return np.maximum(v, 0.0) + np.log1p(np.exp(-np.abs(v)))
+
+
+# --------------------------------------------------------------------------
+# Short causal depthwise convolution + SiLU: Eq. (2)
+# --------------------------------------------------------------------------
+def causal_conv_silu(h, conv_w, conv_b=None, conv_state=None):
+    """u[b, t, i] = SiLU(conv_b[i] + sum_j conv_w[i, j] * h[b, t-(k-1)+j, i]).
+
+    h [B, L, D_e]; conv_w [D_e, k]; taps that reach before t = 0 read
+    conv_state [B, D_e, k-1] (oldest first) or zero.
+    Returns (u, new_conv_state) with new_conv_state the last k-1 inputs.
+    """
+    h = np.asarray(h, F64)
+    bsz, length, d_e = h.shape
+    k = conv_w.shape[1]
+    cw = np.asarray(conv_w, F64)
+    hist = (np.zeros((bsz, k - 1, d_e), F64) if conv_state is None
+            else np.asarray(conv_state, F64).transpose(0, 2, 1))
+    ext = np.concatenate([hist, h], axis=1)            # [B, k-1+L, D_e]; ext[:, k-1+t] = h[:, t]
+    c = np.zeros((bsz, length, d_e), F64)
+    if conv_b is not None:
+        c += np.asarray(conv_b, F64)[None, None, :]
+    for j in range(k):
+        c += cw[None, None, :, j] * ext[:, j:j + length, :]
+    new_state = ext[:, length:, :].transpose(0, 2, 1).copy()   # last k-1 rows, [B, D_e, k-1]
+    return silu(c), new_state
+
+
+# --------------------------------------------------------------------------
+# Selective scan: Eq. (5) with A-bar = exp(dt*A), B-bar*u = dt*B*u, plus D skip
+# --------------------------------------------------------------------------
+def selective_scan(u, dt, b_mat, c_mat, a, d_skip, h0=None):
+    """Per-step recurrence, one step at a time.
+
+    u, dt [B, L, D_e]; b_mat, c_mat [B, L, D_s]; a [D_e, D_s] (negative); d_skip [D_e];
+    h0 [B, D_e, D_s] or None (zeros).
+        h[b,i,n] <- exp(dt[b,t,i]*a[i,n]) * h[b,i,n] + dt[b,t,i]*b_mat[b,t,n]*u[b,t,i]
+        y[b,t,i]  = sum_n c_mat[b,t,n]*h[b,i,n] + d_skip[i]*u[b,t,i]
+    Returns (y, h_final).
+    """
+    u = np.asarray(u, F64)
+    dt = np.asarray(dt, F64)
+    b_mat = np.asarray(b_mat, F64)
+    c_mat = np.asarray(c_mat, F64)
+    a = np.asarray(a, F64)
+    d_skip = np.asarray(d_skip, F64)
+    bsz, length, d_e = u.shape
+    h = (np.zeros((bsz, d_e, a.shape[1]), F64) if h0 is None else np.array(h0, F64, copy=True))
+    y = np.empty((bsz, length, d_e), F64)
+    for t in range(length):
+        decay = np.exp(dt[:, t, :, None] * a[None, :, :])
+        h = decay * h + (dt[:, t, :] * u[:, t, :])[:, :, None] * b_mat[:, t, None, :]
+        y[:, t, :] = (h * c_mat[:, t, None, :]).sum(axis=2) + d_skip[None, :] * u[:, t, :]
+    return y, h
+
+
+# --------------------------------------------------------------------------
+# The layer: Eq. (9)-(13) over Eq. (1)-(6)
+# --------------------------------------------------------------------------
+def rom_layer_forward(x, w: Dict[str, Optional[np.ndarray]], top_k: int, gate_mode: int = 0,
+                      conv_state=None, ssm_state=None, expert_idx=None) -> Dict[str, np.ndarray]:
+    """x [B, L, D_m] -> out [B, L, D_m] and everything in between.
+
+    `w` uses the layouts of rom_synth.make_weights.  `expert_idx` [N, K], if given,
+    replaces the oracle's own top-K decision (used only for tokens whose logits
+    are too close to call in fp32).
+    """
+    x = np.asarray(x, F64)
+    bsz, length, d_m = x.shape
+    n_tok = bsz * length
+    xt = x.reshape(n_tok, d_m)
+    n_exp = w["w_router"].shape[0]
+    d_e = w["w_out"].shape[2]
+    d_s = w["A_log"].shape[1]
+    r = w["w_dt"].shape[2]
+
+    logits = router_logits(xt, w["w_router"], w.get("b_router"))
+    idx = topk_select(logits, top_k) if expert_idx is None else np.asarray(expert_idx, np.int32)
+    gate = gate_weights(logits, idx, gate_mode)
+    counts, offsets, perm, inv_perm = expert_permutation(idx, n_exp)
+
+    xz = routed_linear(xt, w["w_in"], idx)                       # Eq. (11) | Eq. (10) before SiLU
+    h_pre = xz[:, :d_e].reshape(bsz, length, d_e)
+    z = xz[:, d_e:]
+    u, conv_out = causal_conv_silu(h_pre, w["conv_w"], w.get("conv_b"), conv_state)   # Eq. (2)
+    ut = u.reshape(n_tok, d_e)
+    xdbl = routed_linear(ut, w["w_x"], idx)                      # dt_low | B | C
+    dt_low, b_mat, c_mat = xdbl[:, :r], xdbl[:, r:r + d_s], xdbl[:, r + d_s:]
+    dt = softplus(routed_linear(dt_low, w["w_dt"], idx) + np.asarray(w["dt_bias"], F64)[None, :])
+    a = -np.exp(np.asarray(w["A_log"], F64))
+    y, ssm_out = selective_scan(u, dt.reshape(bsz, length, d_e), b_mat.reshape(bsz, length, d_s),
+                                c_mat.reshape(bsz, length, d_s), a, w["D"], ssm_state)   # Eq. (5)
+    g = y.reshape(n_tok, d_e) * silu(z)                          # Y * G, Eq. (10)/(13)
+    out = np.zeros((n_tok, d_m), F64)
+    for k in range(top_k):                                       # Eq. (12)
+        out += gate[:, k:k + 1] * routed_linear(g, w["w_out"], idx[:, k:k + 1])
+    return {
+        "logits": logits, "expert_idx": idx, "gate": gate, "counts": counts, "offsets": offsets,
+        "perm": perm, "inv_perm": inv_perm, "xz": xz, "u": ut, "xdbl": xdbl, "dt": dt,
+        "y": y.reshape(n_tok, d_e), "g": g, "out": out.reshape(bsz, length, d_m),
+        "conv_state": conv_out, "ssm_state": ssm_out,
+    }
+
+
+def rom_step(x, w, top_k, gate_mode, conv_state, ssm_state, expert_idx=None):
+    """One new token per sequence: x [B, D_m]; states as in rom_layer_forward.
+    Returns the same dict with out [B, D_m] and the updated states."""
+    res = rom_layer_forward(np.asarray(x, F64)[:, None, :], w, top_k, gate_mode,
+                            conv_state, ssm_state, expert_idx)
+    res["out"] = res["out"][:, 0, :]
+    return res

@@ -1,0 +1,169 @@
+"""Workload table and seeded tensor generators for the RoM layer.
+
+Shapes follow the paper's Mamba parameterisation (Sec. 3.1: d_e = 2 d_m,
+d_r = d_m / 16, d_s = 16, k = 4) and its 8-expert top-1 models up to
+d_model = 2048 at 16K context (Sec. 5.2, Table 5).  The paper's inputs are
+hidden states of trained language models; seeded random tensors of the same
+shapes stand in for them.
+
+Array layouts produced here (row-major, "out-features major" like a linear
+layer's weight):
+
+    w_router [E, d_model]          b_router [E] (fp32) or None
+    w_in     [E, 2*d_inner, d_model]   rows [0,d_inner) feed the conv branch,
+                                       rows [d_inner, 2*d_inner) the gate branch
+    conv_w   [d_inner, d_conv] (fp32)  conv_b [d_inner] (fp32)
+    w_x      [E_x, dt_rank + 2*d_state, d_inner]   rows = dt_low | B | C
+    w_dt     [E_x, d_inner, dt_rank]
+    dt_bias  [d_inner] (fp32)   A_log [d_inner, d_state] (fp32)   D [d_inner] (fp32)
+    w_out    [E, d_model, d_inner]
+
+All arrays are returned as float32.  For bf16 workloads the tensors that the
+layer stores in bf16 (x, w_router, w_in, w_x, w_dt, w_out) hold values that
+are exactly representable in bf16, so the oracle (which upcasts to fp64) and
+the GPU path (which receives the 16-bit patterns) see identical numbers.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Dict, Optional
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class RomConfig:
+    name: str
+    cfg_id: int          # seed base = 1000 * cfg_id + tensor id
+    batch: int
+    seq_len: int         # L (for the step workload: number of consecutive steps)
+    d_model: int
+    d_inner: int
+    d_state: int
+    d_conv: int
+    dt_rank: int
+    n_experts: int
+    top_k: int
+    dtype: str           # "fp32" | "bf16"
+    gate_mode: int       # 0: softmax over all experts, masked; 1: renormalised over the K selected
+    routed_xdt: bool = True
+    weight_std: float = 0.02
+    rms_norm_x: bool = False
+    router_bias: Optional[tuple] = None
+    step: bool = False   # single-token recurrent workload
+
+    @property
+    def n_experts_xdt(self) -> int:
+        return self.n_experts if self.routed_xdt else 1
+
+    @property
+    def n_tokens(self) -> int:
+        return self.batch * (1 if self.step else self.seq_len)
+
+
+# Router bias of the skewed workload.  With x ~ N(0,1) and W_r ~ N(0, 0.02) at
+# d_model = 2048 the logits are ~N(0, 0.905^2); adding +5.0 to expert 0 puts it
+# in (nearly) every token's top-2 (about half of all slots) and +0.92 to experts
+# 1..3 gives each about a tenth of the slots; the other twelve share the rest.
+_SKEW_BIAS = (5.0, 0.92, 0.92, 0.92) + (0.0,) * 12
+
+CONFIGS: Dict[str, RomConfig] = {
+    # 0: tiny fp32 correctness case
+    "cfg0": RomConfig("cfg0", 0, 1, 64, 64, 128, 16, 4, 4, 4, 1, "fp32", 0),
+    # 1: mid bf16 case
+    "cfg1": RomConfig("cfg1", 1, 4, 4096, 1024, 2048, 16, 4, 64, 8, 1, "bf16", 0),
+    # 2: headline, 1.3B-active-class layer at 16K context
+    "cfg2": RomConfig("cfg2", 2, 1, 16384, 2048, 4096, 16, 4, 128, 8, 1, "bf16", 0,
+                      weight_std=0.02 / float(np.sqrt(2 * 48)), rms_norm_x=True),
+    # 3: skewed routing, 16 experts top-2, renormalised gates
+    "cfg3": RomConfig("cfg3", 3, 2, 8192, 2048, 4096, 16, 4, 128, 16, 2, "bf16", 1,
+                      router_bias=_SKEW_BIAS),
+    # 4: recurrent decode, 256 sequences x 512 steps
+    "cfg4": RomConfig("cfg4", 4, 256, 512, 2048, 4096, 16, 4, 128, 8, 1, "bf16", 0, step=True),
+}
+
+
+def get_config(name: str, **overrides) -> RomConfig:
+    cfg = CONFIGS[name]
+    return replace(cfg, **overrides) if overrides else cfg
+
+
+# --------------------------------------------------------------------------
+# bf16 storage helpers (round-to-nearest-even on the upper 16 bits of fp32)
+# --------------------------------------------------------------------------
+def bf16_bits(a: np.ndarray) -> np.ndarray:
+    """uint16 bit patterns of `a` rounded to bf16 (nearest even). Finite inputs only."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    bias = np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return ((u + bias) >> np.uint32(16)).astype(np.uint16)
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """float32 array whose values are `a` rounded to bf16."""
+    return (bf16_bits(a).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def _rng(cfg: RomConfig, tensor_id: int) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(1000 * cfg.cfg_id + tensor_id))
+
+
+def _normal(cfg: RomConfig, tensor_id: int, shape, std: float) -> np.ndarray:
+    out = _rng(cfg, tensor_id).standard_normal(shape, dtype=np.float32)
+    out *= np.float32(std)
+    return out
+
+
+def _store(cfg: RomConfig, a: np.ndarray) -> np.ndarray:
+    return round_to_bf16(a) if cfg.dtype == "bf16" else a
+
+
+# tensor ids (seed = 1000 * cfg_id + id)
+_T_X, _T_WR, _T_WIN, _T_CW, _T_CB, _T_WX, _T_WDT, _T_DTB, _T_WOUT, _T_CS, _T_SS, _T_XS = range(1, 13)
+
+
+def make_weights(cfg: RomConfig) -> Dict[str, Optional[np.ndarray]]:
+    E, Ex = cfg.n_experts, cfg.n_experts_xdt
+    Dm, De, Ds, k, R = cfg.d_model, cfg.d_inner, cfg.d_state, cfg.d_conv, cfg.dt_rank
+    s = cfg.weight_std
+    w: Dict[str, Optional[np.ndarray]] = {}
+    w["w_router"] = _store(cfg, _normal(cfg, _T_WR, (E, Dm), 0.02))
+    w["b_router"] = (np.asarray(cfg.router_bias, dtype=np.float32)
+                     if cfg.router_bias is not None else None)
+    w["w_in"] = _store(cfg, _normal(cfg, _T_WIN, (E, 2 * De, Dm), s))
+    # The paper does not give the short-conv initialisation; uniform(-1/sqrt(k), 1/sqrt(k))
+    # keeps the conv output at the scale of its input so SiLU is exercised off its linear part.
+    lim = 1.0 / np.sqrt(k)
+    w["conv_w"] = _rng(cfg, _T_CW).uniform(-lim, lim, (De, k)).astype(np.float32)
+    w["conv_b"] = _rng(cfg, _T_CB).uniform(-lim, lim, (De,)).astype(np.float32)
+    w["w_x"] = _store(cfg, _normal(cfg, _T_WX, (Ex, R + 2 * Ds, De), s))
+    w["w_dt"] = _store(cfg, _normal(cfg, _T_WDT, (Ex, De, R), s))
+    # dt_bias: inverse softplus of a log-uniform time step in [1e-3, 1e-1]
+    tau = np.exp(_rng(cfg, _T_DTB).uniform(np.log(1e-3), np.log(1e-1), (De,)))
+    w["dt_bias"] = (tau + np.log(-np.expm1(-tau))).astype(np.float32)
+    w["A_log"] = np.log(np.tile(np.arange(1, Ds + 1, dtype=np.float64), (De, 1))).astype(np.float32)
+    w["D"] = np.ones((De,), dtype=np.float32)
+    w["w_out"] = _store(cfg, _normal(cfg, _T_WOUT, (E, Dm, De), s))
+    return w
+
+
+def make_input(cfg: RomConfig) -> np.ndarray:
+    """x [B, L, d_model] (for the step workload: the first step's [B, 1, d_model])."""
+    L = 1 if cfg.step else cfg.seq_len
+    x = _normal(cfg, _T_X, (cfg.batch, L, cfg.d_model), 1.0)
+    if cfg.rms_norm_x:
+        x /= np.sqrt(np.mean(np.square(x, dtype=np.float32), axis=-1, keepdims=True))
+    return _store(cfg, x)
+
+
+def make_states(cfg: RomConfig):
+    """(conv_state [B, d_inner, d_conv-1], ssm_state [B, d_inner, d_state]), fp32, ~N(0,1)."""
+    cs = _normal(cfg, _T_CS, (cfg.batch, cfg.d_inner, cfg.d_conv - 1), 1.0)
+    ss = _normal(cfg, _T_SS, (cfg.batch, cfg.d_inner, cfg.d_state), 1.0)
+    return cs, ss
+
+
+def make_step_inputs(cfg: RomConfig, n_steps: Optional[int] = None) -> np.ndarray:
+    """x_steps [n_steps, B, d_model]: one new token per sequence per step (no feedback)."""
+    n = cfg.seq_len if n_steps is None else n_steps
+    # values are drawn sequentially, so a shorter run is a prefix of a longer one
+    return _store(cfg, _normal(cfg, _T_XS, (n, cfg.batch, cfg.d_model), 1.0))
