@@ -1,0 +1,176 @@
+/*
+ * librom - Routing Mamba (RoM) layer forward pass and recurrent step for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer in rom_weights and every tensor / workspace argument is a
+ * DEVICE pointer to caller-owned memory unless a comment says "host".  The library
+ * allocates no device memory, launches everything asynchronously on the caller's HIP
+ * stream and never synchronises (the rom_profile_* helpers excepted).  Buffers must
+ * stay valid until the stream has passed the end of the call.
+ *
+ * The layer (paper Sec. 4.2, Eq. (9)-(13), on top of the Mamba layer of Sec. 3.1,
+ * Eq. (1)-(6)):
+ *
+ *   router      l[n,e] = x[n,:] . w_router[e,:] + b_router[e]; the top-K experts per token
+ *               are picked on the logits (descending, lowest index on ties); P = softmax(l);
+ *               gate[n,k] = P[n, idx[n,k]]   (gate_mode 0, Eq. (9) as printed) or that value
+ *               divided by the sum over the K selected (gate_mode 1, text before Eq. (9)).
+ *   in/gate     xz[n,:] = sum_k w_in[idx[n,k]] x[n,:]            (Eq. (10)/(11), unweighted sum)
+ *   conv        u = SiLU(conv_b + causal depthwise conv_k(xz[:, :d_inner]))        (Eq. (2))
+ *   x / dt      [dt_low | B | C][n,:] = sum_k w_x[e_k] u[n,:];
+ *               dt[n,:] = softplus(sum_k w_dt[e_k] dt_low[n,:] + dt_bias)
+ *               (e_k = idx[n,k] when n_experts_xdt == n_experts - the "Conv, Gate, dt, x, Out"
+ *               variant of Table 1 - or the single shared module when n_experts_xdt == 1,
+ *               the paper's default of Sec. 4.3, in which case there is no sum over k)
+ *   scan        h <- exp(dt*A) h + dt*B*u ;  y = C.h + D*u ;  A = -exp(A_log)          (Eq. (5))
+ *   gate        g = y * SiLU(xz[:, d_inner:])                                (Eq. (6)/(10)/(13))
+ *   out         out[n,:] = sum_k gate[n,k] * (w_out[idx[n,k]] g[n,:])           (Eq. (12)/(13))
+ *
+ * Token order: n = b*L + t.  Slot order: s = n*K + k, k in descending-logit order.
+ * All matrices are row-major; projection weights are stored "out-features major"
+ * ([expert][out][in], the layout of a linear layer's weight).
+ */
+#ifndef ROM_H_
+#define ROM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ROM_API __attribute__((visibility("default")))
+
+#define ROM_OK             0
+#define ROM_E_INVAL       (-1)  /* NULL pointer, bad enum, bad size, misaligned pointer      */
+#define ROM_E_WORKSPACE   (-2)  /* workspace smaller than rom_workspace_bytes()               */
+#define ROM_E_UNSUPPORTED (-3)  /* shape outside what this build implements (see rom_dims)    */
+#define ROM_E_HIP         (-4)  /* a HIP launch reported an error                             */
+
+#define ROM_DTYPE_F32  0        /* fp32 weights, activations, arithmetic                      */
+#define ROM_DTYPE_BF16 1        /* bf16 weights/activations, fp32 accumulation and scan state */
+
+/* Shape of one layer.  Supported: d_state == 16, d_conv == 4, 1 <= top_k <= n_experts <= 64,
+ * top_k <= 8, d_inner % 16 == 0, d_model % 8 == 0, dt_rank % 8 == 0,
+ * n_experts_xdt in {1, n_experts}.  Anything else returns ROM_E_UNSUPPORTED / ROM_E_INVAL. */
+typedef struct rom_dims {
+  int32_t d_model;        /* D_m                                             */
+  int32_t d_inner;        /* D_e (paper: 2 D_m)                              */
+  int32_t d_state;        /* D_s (paper: 16)                                 */
+  int32_t d_conv;         /* k   (paper: 4)                                  */
+  int32_t dt_rank;        /* R   (paper: D_m / 16)                           */
+  int32_t n_experts;      /* E                                               */
+  int32_t top_k;          /* K                                               */
+  int32_t n_experts_xdt;  /* E (routed x/dt projections) or 1 (shared)       */
+  int32_t dtype;          /* ROM_DTYPE_*                                     */
+  int32_t gate_mode;      /* 0: masked softmax (Eq. (9)); 1: renormalised over the K selected */
+} rom_dims;
+
+/* Layer parameters.  "T" is float for ROM_DTYPE_F32 and bf16 (16-bit) for ROM_DTYPE_BF16.
+ * All pointers must be 16-byte aligned. */
+typedef struct rom_weights {
+  const void  *w_router;  /* T   [E, d_model]                                                  */
+  const float *b_router;  /* f32 [E] or NULL                                                   */
+  const void  *w_in;      /* T   [E, 2*d_inner, d_model]; rows [0,d_inner) conv branch (Eq. (11)),
+                                 rows [d_inner, 2*d_inner) gate branch (Eq. (10))              */
+  const float *conv_w;    /* f32 [d_inner, d_conv]; tap j multiplies the input at t-(d_conv-1)+j */
+  const float *conv_b;    /* f32 [d_inner] or NULL                                             */
+  const void  *w_x;       /* T   [E_xdt, dt_rank + 2*d_state, d_inner]; rows = dt_low | B | C  */
+  const void  *w_dt;      /* T   [E_xdt, d_inner, dt_rank]                                     */
+  const float *dt_bias;   /* f32 [d_inner]                                                     */
+  const float *A_log;     /* f32 [d_inner, d_state]; A = -exp(A_log)                           */
+  const float *D;         /* f32 [d_inner]                                                     */
+  const void  *w_out;     /* T   [E, d_model, d_inner]                                         */
+} rom_weights;
+
+/* Byte offsets, inside the workspace of rom_layer_forward / rom_step, of the intermediate
+ * tensors a caller may want to inspect after the call (tests compare them stage by stage).
+ * An offset of (size_t)-1 means "not materialised for these dims". */
+typedef struct rom_ws_layout {
+  size_t total_bytes;
+  size_t expert_idx;   /* i32 [N*K]                                        */
+  size_t gate;         /* f32 [N*K]                                        */
+  size_t counts;       /* i32 [E]                                          */
+  size_t offsets;      /* i32 [E+1]                                        */
+  size_t perm;         /* i32 [N*K] sorted position -> slot                */
+  size_t inv_perm;     /* i32 [N*K] slot -> sorted position                */
+  size_t logits;       /* f32 [N, E]                                       */
+  size_t xz;           /* T   [N, 2*d_inner]  (sum over k already applied) */
+  size_t u;            /* T   [N, d_inner]                                 */
+  size_t dt_low;       /* T   [N, dt_rank]                                 */
+  size_t bc;           /* f32 [N, 2*d_state]  B then C                     */
+  size_t dt;           /* T   [N, d_inner]    after softplus               */
+  size_t g;            /* T   [N, d_inner]    gated scan output            */
+} rom_ws_layout;
+
+/* Workspace size in bytes for a call with B sequences of L tokens (rom_step: L = 1;
+ * rom_route: the same formula with B*L = N).  Returns 0 if dims are invalid or unsupported.
+ * host-only; dims is a host pointer. */
+ROM_API size_t rom_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L);
+
+/* Fills *layout (host) for the same arguments; returns ROM_OK or an error. */
+ROM_API int rom_workspace_layout(const rom_dims *dims, int64_t B, int64_t L, rom_ws_layout *layout);
+
+/* Router and expert grouping only (Eq. (9) and the permutation the grouped projections use).
+ *   x          T   [N, d_model]
+ *   expert_idx i32 [N, K]   out  experts per token, k-th column = (k+1)-th largest logit
+ *   gate       f32 [N, K]   out  gating weights R of Eq. (9) for those experts
+ *   counts     i32 [E]      out  slots per expert (sum = N*K: no capacity limit, nothing dropped)
+ *   offsets    i32 [E+1]    out  exclusive prefix sum of counts
+ *   perm       i32 [N*K]    out  perm[p] = slot at sorted position p (grouped by expert,
+ *                                ascending slot inside an expert)
+ *   inv_perm   i32 [N*K]    out  inverse of perm
+ *   logits     f32 [N, E]   out, may be NULL
+ *   ws/ws_bytes             workspace of at least rom_workspace_bytes(dims, N, 1)
+ * N == 0 is a successful no-op.  Errors are reported before anything is launched. */
+ROM_API int rom_route(const rom_dims *dims, const rom_weights *w, const void *x, int64_t N,
+              int32_t *expert_idx, float *gate, int32_t *counts, int32_t *offsets,
+              int32_t *perm, int32_t *inv_perm, float *logits,
+              void *ws, size_t ws_bytes, void *hip_stream);
+
+/* The whole layer, Eq. (9)-(13).
+ *   x              T   [B, L, d_model]
+ *   conv_state_in  f32 [B, d_inner, d_conv-1] oldest first, or NULL (zeros): the conv-branch
+ *                  inputs (xz[:, :d_inner]) of the d_conv-1 tokens before this call
+ *   ssm_state_in   f32 [B, d_inner, d_state] or NULL (zeros)
+ *   out            T   [B, L, d_model]; must not alias x
+ *   conv_state_out / ssm_state_out: same shapes, written if not NULL (may alias the *_in)
+ * B == 0 or L == 0 is a successful no-op. */
+ROM_API int rom_layer_forward(const rom_dims *dims, const rom_weights *w, const void *x,
+                      int64_t B, int64_t L,
+                      const float *conv_state_in, const float *ssm_state_in,
+                      void *out, float *conv_state_out, float *ssm_state_out,
+                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/* One new token per sequence (constant-time recurrent inference, Eq. (5) advanced one step):
+ *   x [B, d_model] -> out [B, d_model]; conv_state / ssm_state are updated in place. */
+ROM_API int rom_step(const rom_dims *dims, const rom_weights *w, const void *x, int64_t B,
+             float *conv_state, float *ssm_state, void *out,
+             void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Static description of an error code. */
+ROM_API const char *rom_strerror(int code);
+
+/* Per-stage timing for benchmarks.  While enabled, rom_layer_forward and rom_step record
+ * HIP events on the launch stream around each stage (kernel or small kernel group).
+ * rom_profile_collect synchronises on those events, adds the elapsed milliseconds of every
+ * recorded call into stage_ms (host, ROM_STAGE_COUNT doubles), stores the number of calls in
+ * *n_calls (host) and resets the recorder.  max_calls == 0 disables recording and frees the events. */
+#define ROM_STAGE_ROUTE     0  /* router logits, top-K, gates                         */
+#define ROM_STAGE_PERMUTE   1  /* histogram, offsets, stable permutation              */
+#define ROM_STAGE_IN_PROJ   2  /* grouped GEMM, Eq. (10)/(11) (+ sum over k if K > 1)  */
+#define ROM_STAGE_CONV      3  /* causal depthwise conv + SiLU, Eq. (2)                */
+#define ROM_STAGE_X_PROJ    4  /* grouped GEMM dt_low | B | C                          */
+#define ROM_STAGE_DT_PROJ   5  /* grouped GEMM + bias + softplus                       */
+#define ROM_STAGE_SCAN      6  /* selective scan + D skip + SiLU(z) gating, Eq. (5)/(6) */
+#define ROM_STAGE_OUT_PROJ  7  /* grouped GEMM Eq. (13) (+ gate scaling if K == 1)     */
+#define ROM_STAGE_COMBINE   8  /* un-permute + gate-weighted sum, Eq. (12) (K > 1)     */
+#define ROM_STAGE_COUNT     9
+ROM_API int rom_profile_enable(int max_calls);
+ROM_API int rom_profile_collect(double *stage_ms, int *n_calls);
+ROM_API const char *rom_stage_name(int stage);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROM_H_ */

@@ -1,0 +1,19 @@
+"""MI355X-native Routing Mamba (RoM) layer forward pass: Python binding over librom.so.
+
+The binding only marshals arguments (torch tensors -> device pointers); every step of
+the layer runs in the HIP kernels behind the C ABI declared in include/rom.h.
+"""
+from .binding import (  # noqa: F401
+    RomDims,
+    RomError,
+    RomLayer,
+    load_library,
+    rom_layer_forward,
+    rom_profile_collect,
+    rom_profile_enable,
+    rom_route,
+    rom_step,
+    rom_workspace_bytes,
+    rom_workspace_layout,
+    STAGE_NAMES,
+)

@@ -1,0 +1,241 @@
+"""ctypes binding of librom.so.  Argument marshalling only - no arithmetic happens here."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librom.so")
+_lib: Optional[ctypes.CDLL] = None
+
+ROM_DTYPE_F32, ROM_DTYPE_BF16 = 0, 1
+STAGE_NAMES = ("route", "permute", "in_proj", "conv", "x_proj", "dt_proj", "scan_gate", "out_proj",
+               "combine")
+
+
+class RomError(RuntimeError):
+    pass
+
+
+class RomDims(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "d_model", "d_inner", "d_state", "d_conv", "dt_rank", "n_experts", "top_k",
+        "n_experts_xdt", "dtype", "gate_mode")]
+
+
+class _RomWeights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in (
+        "w_router", "b_router", "w_in", "conv_w", "conv_b", "w_x", "w_dt", "dt_bias", "A_log", "D",
+        "w_out")]
+
+
+class _RomWsLayout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_size_t) for n in (
+        "total_bytes", "expert_idx", "gate", "counts", "offsets", "perm", "inv_perm", "logits", "xz",
+        "u", "dt_low", "bc", "dt", "g")]
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads librom.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RomError(f"{_LIB_PATH} is missing: build it with `python -m paper_2506_18145_amd.build` "
+                       "(or __graft_entry__.build()); there is no non-HIP fallback")
+    lib = ctypes.CDLL(_LIB_PATH)
+    P, I64, SZ = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
+    lib.rom_workspace_bytes.restype = SZ
+    lib.rom_workspace_bytes.argtypes = [ctypes.POINTER(RomDims), I64, I64]
+    lib.rom_workspace_layout.restype = ctypes.c_int
+    lib.rom_workspace_layout.argtypes = [ctypes.POINTER(RomDims), I64, I64, ctypes.POINTER(_RomWsLayout)]
+    lib.rom_route.restype = ctypes.c_int
+    lib.rom_route.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64,
+                              P, P, P, P, P, P, P, P, SZ, P]
+    lib.rom_layer_forward.restype = ctypes.c_int
+    lib.rom_layer_forward.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64, I64,
+                                      P, P, P, P, P, P, SZ, P]
+    lib.rom_step.restype = ctypes.c_int
+    lib.rom_step.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64, P, P, P, P, SZ, P]
+    lib.rom_strerror.restype = ctypes.c_char_p
+    lib.rom_strerror.argtypes = [ctypes.c_int]
+    lib.rom_profile_enable.restype = ctypes.c_int
+    lib.rom_profile_enable.argtypes = [ctypes.c_int]
+    lib.rom_profile_collect.restype = ctypes.c_int
+    lib.rom_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
+    lib.rom_stage_name.restype = ctypes.c_char_p
+    lib.rom_stage_name.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def _check(code: int, what: str) -> None:
+    if code != 0:
+        raise RomError(f"{what} failed: {load_library().rom_strerror(code).decode()} ({code})")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise RomError("tensor arguments must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _weights_struct(w: Dict[str, Optional[torch.Tensor]]) -> _RomWeights:
+    s = _RomWeights()
+    for name, _ in _RomWeights._fields_:
+        setattr(s, name, _ptr(w.get(name)))
+    return s
+
+
+def rom_workspace_bytes(dims: RomDims, B: int, L: int) -> int:
+    return int(load_library().rom_workspace_bytes(ctypes.byref(dims), B, L))
+
+
+def rom_workspace_layout(dims: RomDims, B: int, L: int) -> Dict[str, int]:
+    lay = _RomWsLayout()
+    _check(load_library().rom_workspace_layout(ctypes.byref(dims), B, L, ctypes.byref(lay)),
+           "rom_workspace_layout")
+    return {n: int(getattr(lay, n)) for n, _ in _RomWsLayout._fields_}
+
+
+def rom_route(dims, weights, x, expert_idx, gate, counts, offsets, perm, inv_perm, logits, ws):
+    n_tok = x.numel() // dims.d_model if dims.d_model else 0
+    code = load_library().rom_route(
+        ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(x), n_tok, _ptr(expert_idx),
+        _ptr(gate), _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv_perm), _ptr(logits), _ptr(ws),
+        ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check(code, "rom_route")
+
+
+def rom_layer_forward(dims, weights, x, B, L, conv_state_in, ssm_state_in, out, conv_state_out,
+                      ssm_state_out, ws):
+    code = load_library().rom_layer_forward(
+        ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(x), B, L, _ptr(conv_state_in),
+        _ptr(ssm_state_in), _ptr(out), _ptr(conv_state_out), _ptr(ssm_state_out), _ptr(ws),
+        ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check(code, "rom_layer_forward")
+
+
+def rom_step(dims, weights, x, B, conv_state, ssm_state, out, ws):
+    code = load_library().rom_step(
+        ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(x), B, _ptr(conv_state),
+        _ptr(ssm_state), _ptr(out), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
+        _stream())
+    _check(code, "rom_step")
+
+
+def rom_profile_enable(max_calls: int) -> None:
+    _check(load_library().rom_profile_enable(max_calls), "rom_profile_enable")
+
+
+def rom_profile_collect():
+    """Returns ({stage name: summed milliseconds}, number of recorded calls)."""
+    ms = (ctypes.c_double * len(STAGE_NAMES))()
+    n = ctypes.c_int(0)
+    _check(load_library().rom_profile_collect(ms, ctypes.byref(n)), "rom_profile_collect")
+    return {name: ms[i] for i, name in enumerate(STAGE_NAMES)}, n.value
+
+
+class RomLayer:
+    """Holds one layer's parameters on the GPU plus a workspace, and forwards to the C ABI."""
+
+    _TORCH_DTYPE = {"fp32": torch.float32, "bf16": torch.bfloat16}
+
+    def __init__(self, cfg, weights_np, device="cuda:0"):
+        load_library()
+        if not torch.cuda.is_available():
+            raise RomError("RomLayer needs a GPU: librom has no CPU path")
+        self.device = torch.device(device)
+        self.tdtype = self._TORCH_DTYPE[cfg.dtype]
+        self.dims = RomDims(cfg.d_model, cfg.d_inner, cfg.d_state, cfg.d_conv, cfg.dt_rank,
+                            cfg.n_experts, cfg.top_k, cfg.n_experts_xdt,
+                            ROM_DTYPE_BF16 if cfg.dtype == "bf16" else ROM_DTYPE_F32, cfg.gate_mode)
+        typed = {"w_router", "w_in", "w_x", "w_dt", "w_out"}
+        self.weights: Dict[str, Optional[torch.Tensor]] = {}
+        for name, arr in weights_np.items():
+            if arr is None:
+                self.weights[name] = None
+                continue
+            t = torch.from_numpy(arr)
+            t = t.to(self.tdtype) if name in typed else t.to(torch.float32)
+            self.weights[name] = t.to(self.device).contiguous()
+        self._ws: Optional[torch.Tensor] = None
+
+    def to_device(self, arr, typed=True) -> torch.Tensor:
+        t = torch.from_numpy(arr)
+        return t.to(self.tdtype if typed else torch.float32).to(self.device).contiguous()
+
+    def workspace(self, B: int, L: int) -> torch.Tensor:
+        need = rom_workspace_bytes(self.dims, B, L)
+        if need == 0:
+            raise RomError("rom_workspace_bytes returned 0: unsupported dims")
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def ws_view(self, name: str, B: int, L: int) -> torch.Tensor:
+        """Intermediate tensor `name` of the last forward/step call with these B, L."""
+        lay = rom_workspace_layout(self.dims, B, L)
+        d, n = self.dims, B * L
+        shapes = {
+            "expert_idx": (torch.int32, (n, d.top_k)), "gate": (torch.float32, (n, d.top_k)),
+            "counts": (torch.int32, (d.n_experts,)), "offsets": (torch.int32, (d.n_experts + 1,)),
+            "perm": (torch.int32, (n * d.top_k,)), "inv_perm": (torch.int32, (n * d.top_k,)),
+            "logits": (torch.float32, (n, d.n_experts)), "xz": (self.tdtype, (n, 2 * d.d_inner)),
+            "u": (self.tdtype, (n, d.d_inner)), "dt_low": (self.tdtype, (n, d.dt_rank)),
+            "bc": (torch.float32, (n, 2 * d.d_state)), "dt": (self.tdtype, (n, d.d_inner)),
+            "g": (self.tdtype, (n, d.d_inner)),
+        }
+        dtype, shape = shapes[name]
+        count = 1
+        for s in shape:
+            count *= s
+        nbytes = count * torch.empty((), dtype=dtype).element_size()
+        off = lay[name]
+        return self._ws[off:off + nbytes].view(dtype).view(shape)
+
+    def route(self, x: torch.Tensor):
+        d = self.dims
+        n = x.numel() // d.d_model
+        i32 = dict(dtype=torch.int32, device=self.device)
+        res = {
+            "expert_idx": torch.empty((n, d.top_k), **i32),
+            "gate": torch.empty((n, d.top_k), dtype=torch.float32, device=self.device),
+            "counts": torch.empty((d.n_experts,), **i32),
+            "offsets": torch.empty((d.n_experts + 1,), **i32),
+            "perm": torch.empty((n * d.top_k,), **i32),
+            "inv_perm": torch.empty((n * d.top_k,), **i32),
+            "logits": torch.empty((n, d.n_experts), dtype=torch.float32, device=self.device),
+        }
+        rom_route(d, self.weights, x, res["expert_idx"], res["gate"], res["counts"], res["offsets"],
+                  res["perm"], res["inv_perm"], res["logits"], self.workspace(max(n, 1), 1))
+        return res
+
+    def forward(self, x: torch.Tensor, conv_state=None, ssm_state=None, return_states=False):
+        B, L, _ = x.shape
+        out = torch.empty_like(x)
+        conv_out = ssm_out = None
+        if return_states:
+            conv_out = torch.empty((B, self.dims.d_inner, self.dims.d_conv - 1), dtype=torch.float32,
+                                   device=self.device)
+            ssm_out = torch.empty((B, self.dims.d_inner, self.dims.d_state), dtype=torch.float32,
+                                  device=self.device)
+        rom_layer_forward(self.dims, self.weights, x, B, L, conv_state, ssm_state, out, conv_out,
+                          ssm_out, self.workspace(max(B, 1), max(L, 1)))
+        return (out, conv_out, ssm_out) if return_states else out
+
+    def step(self, x: torch.Tensor, conv_state: torch.Tensor, ssm_state: torch.Tensor,
+             out: Optional[torch.Tensor] = None):
+        B = x.shape[0]
+        if out is None:
+            out = torch.empty_like(x)
+        rom_step(self.dims, self.weights, x, B, conv_state, ssm_state, out, self.workspace(max(B, 1), 1))
+        return out

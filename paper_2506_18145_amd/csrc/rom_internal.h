@@ -1,0 +1,88 @@
+// Internal declarations shared by the librom translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rom.h"
+
+namespace rom {
+
+typedef unsigned short bf16_t;  // raw bf16 bit pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) {
+  return __uint_as_float(static_cast<unsigned int>(v) << 16);
+}
+// round-to-nearest-even; inputs are finite
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  unsigned int u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return static_cast<bf16_t>(u >> 16);
+}
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+__device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
+__device__ __forceinline__ float fast_rcp(float v) { return __builtin_amdgcn_rcpf(v); }
+// SiLU(v) = v / (1 + exp(-v))
+__device__ __forceinline__ float silu_f32(float v) {
+  return v * fast_rcp(1.0f + fast_exp2(-1.44269504088896341f * v));
+}
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---------------------------------------------------------------- routing (Eq. (9))
+// logits may be NULL.  tok_of_pos[p] = perm[p] / K.  block_counts: i32 [route_blocks(S), E].
+int64_t route_blocks(int64_t n_slots);
+hipError_t launch_route_topk(int dtype, const void *x, const void *w_router, const float *b_router,
+                             int64_t n_tokens, int d_model, int n_experts, int top_k, int gate_mode,
+                             int32_t *expert_idx, float *gate, float *logits, hipStream_t s);
+hipError_t launch_permutation(const int32_t *expert_idx, int64_t n_slots, int n_experts, int top_k,
+                              int32_t *block_counts, int32_t *counts, int32_t *offsets,
+                              int32_t *perm, int32_t *inv_perm, int32_t *tok_of_pos, hipStream_t s);
+
+// ---------------------------------------------------------------- grouped GEMM
+// C[c_row(p), :] = epilogue( A[a_row(p), :] . W[e(p)]^T ),  p = sorted position in [0, M)
+// e(p) from offsets (device, i32 [n_groups+1]); offsets == NULL means one group of M rows.
+struct GemmArgs {
+  int dtype;                 // ROM_DTYPE_*: type of A and W
+  const void *A;             // [*, lda]
+  int64_t lda;
+  const int32_t *a_rows;     // row of A for position p, NULL = p
+  const void *W;             // [n_groups, N, K] row-major
+  const int32_t *offsets;    // NULL = single group
+  int n_groups;
+  int64_t M;                 // total rows (positions)
+  int N, K;                  // out features, in features
+  void *C;                   // [*, ldc]
+  int64_t ldc;
+  const int32_t *c_rows;     // row of C for position p, NULL = p
+  int c_is_f32;              // 1: C is float regardless of dtype; 0: C has type T
+  const float *bias;         // [N] or NULL: added before softplus
+  int softplus;              // apply softplus after bias
+  const float *row_scale;    // indexed by c_row (NULL = 1): multiplies the row
+};
+hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s);
+
+// ---------------------------------------------------------------- sequence kernels
+// sum over the K slots of a token: dst[n, :] = sum_k src[inv_perm[n*K+k], :]
+hipError_t launch_slot_sum(int src_is_f32, int dst_is_f32, const void *src, int64_t ld_src, void *dst,
+                           int64_t ld_dst, const int32_t *inv_perm, int64_t n_tokens, int top_k,
+                           int n_cols, const float *bias, int softplus, hipStream_t s);
+// xdbl (f32 [*, R + 32], token order or sorted) -> dt_low (T [N, R]) and bc (f32 [N, 32])
+hipError_t launch_split_xdbl(int dtype, const float *xdbl, const int32_t *inv_perm, int top_k,
+                             int64_t n_tokens, int dt_rank, void *dt_low, float *bc, hipStream_t s);
+hipError_t launch_conv_silu(int dtype, const void *xz, int64_t ld_xz, const float *conv_w,
+                            const float *conv_b, const float *state_in, float *state_out, void *u,
+                            int64_t B, int64_t L, int d_inner, hipStream_t s);
+hipError_t launch_scan_gate(int dtype, const void *u, const void *dt, const float *bc, const void *z,
+                            int64_t ld_z, const float *A_log, const float *D, const float *h_in,
+                            float *h_out, void *g, int64_t B, int64_t L, int d_inner, hipStream_t s);
+// out[n, :] = sum_k gate[n*K+k] * op[inv_perm[n*K+k], :]
+hipError_t launch_combine(int dtype, const void *op, const int32_t *inv_perm, const float *gate,
+                          void *out, int64_t n_tokens, int top_k, int d_model, hipStream_t s);
+
+}  // namespace rom

@@ -1,0 +1,249 @@
+// Router (Eq. (9)) and expert grouping for the RoM layer: logits, top-K on logits, softmax
+// gates, then a stable counting sort of the (token, k) slots by expert built from wavefront
+// ballots and prefix sums (no atomics, so the permutation is reproducible bit for bit).
+#include "rom_internal.h"
+
+namespace rom {
+
+namespace {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
+  return v;
+}
+
+template <typename T> struct Vec8;  // 8 consecutive elements
+template <> struct Vec8<bf16_t> {
+  uint4 raw;
+  __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const uint4 *>(p); }
+  __device__ __forceinline__ float get(int i) const {
+    unsigned int w = (&raw.x)[i >> 1];
+    return __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16));
+  }
+};
+template <> struct Vec8<float> {
+  float4 lo, hi;
+  __device__ __forceinline__ void load(const float *p) {
+    lo = *reinterpret_cast<const float4 *>(p);
+    hi = *reinterpret_cast<const float4 *>(p + 4);
+  }
+  __device__ __forceinline__ float get(int i) const { return i < 4 ? (&lo.x)[i] : (&hi.x)[i - 4]; }
+};
+
+// One wavefront handles TOK consecutive tokens: lanes stride over d_model in chunks of 8,
+// each lane keeps TOK x EMAX partial dot products, a fixed butterfly sums them.
+// Lane e then owns logit e of each token and the wave does K arg-max rounds by ballot.
+template <typename T, int EMAX, int TOK>
+__global__ __launch_bounds__(256) void route_topk_kernel(
+    const T *__restrict__ x, const T *__restrict__ w_router, const float *__restrict__ b_router,
+    int64_t n_tokens, int d_model, int n_experts, int top_k, int gate_mode,
+    int32_t *__restrict__ expert_idx, float *__restrict__ gate, float *__restrict__ logits) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave_id = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / kWave;
+  const int64_t tok0 = wave_id * TOK;
+  if (tok0 >= n_tokens) return;
+
+  float acc[TOK][EMAX];
+#pragma unroll
+  for (int t = 0; t < TOK; ++t)
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) acc[t][e] = 0.0f;
+
+  for (int d0 = lane * 8; d0 < d_model; d0 += kWave * 8) {
+    Vec8<T> xv[TOK];
+#pragma unroll
+    for (int t = 0; t < TOK; ++t) {
+      const int64_t tok = (tok0 + t < n_tokens) ? tok0 + t : n_tokens - 1;
+      xv[t].load(x + tok * d_model + d0);
+    }
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) {
+      if (e < n_experts) {
+        Vec8<T> wv;
+        wv.load(w_router + static_cast<int64_t>(e) * d_model + d0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float wf = wv.get(i);
+#pragma unroll
+          for (int t = 0; t < TOK; ++t) acc[t][e] = fmaf(xv[t].get(i), wf, acc[t][e]);
+        }
+      }
+    }
+  }
+
+#pragma unroll
+  for (int t = 0; t < TOK; ++t) {
+    const int64_t tok = tok0 + t;
+    // lane e keeps logit e
+    float mine = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) {
+      const float s = wave_sum(acc[t][e]);
+      if (lane == e && e < n_experts) mine = s + (b_router ? b_router[e] : 0.0f);
+    }
+    if (tok >= n_tokens) continue;
+    if (logits && lane < n_experts) logits[tok * n_experts + lane] = mine;
+
+    const float lmax = wave_max(mine);
+    const float p_un = (lane < n_experts) ? __expf(mine - lmax) : 0.0f;
+    const float denom = wave_sum(p_un);
+
+    float work = mine;
+    float my_gate = 0.0f;       // lane k ends up with the gate of the k-th pick
+    int my_pick = 0;
+    float picked_sum = 0.0f;
+    for (int k = 0; k < top_k; ++k) {
+      const float best = wave_max(work);
+      const unsigned long long hit = __ballot(work == best && lane < n_experts);
+      const int e_sel = __ffsll(static_cast<long long>(hit)) - 1;   // lowest index wins ties
+      const float p_sel = __shfl(p_un, e_sel, kWave);
+      picked_sum += p_sel;
+      if (lane == k) { my_pick = e_sel; my_gate = p_sel; }
+      if (lane == e_sel) work = -INFINITY;
+    }
+    if (lane < top_k) {
+      const float norm = (gate_mode == 1) ? picked_sum : denom;
+      expert_idx[tok * top_k + lane] = my_pick;
+      gate[tok * top_k + lane] = my_gate / norm;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ stable grouping
+constexpr int kSortBlock = 256;   // slots per block, one per thread
+constexpr int kSortWaves = kSortBlock / kWave;
+
+// per-wave population count of every expert among this wave's slots, via ballots
+__device__ __forceinline__ unsigned long long match_expert(int key, int n_experts, int lane,
+                                                           int *wave_counts /* LDS [E] or NULL */) {
+  unsigned long long mine = 0ull;
+  for (int e = 0; e < n_experts; ++e) {
+    const unsigned long long m = __ballot(key == e);
+    if (key == e) mine = m;
+    if (wave_counts && lane == 0) wave_counts[e] = __popcll(m);
+  }
+  return mine;
+}
+
+__global__ __launch_bounds__(kSortBlock) void hist_kernel(const int32_t *__restrict__ expert_idx,
+                                                          int64_t n_slots, int n_experts,
+                                                          int32_t *__restrict__ block_counts) {
+  __shared__ int cnt[kSortWaves][64];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int64_t s = static_cast<int64_t>(blockIdx.x) * kSortBlock + threadIdx.x;
+  const int key = (s < n_slots) ? expert_idx[s] : -1;
+  match_expert(key, n_experts, lane, cnt[wave]);
+  __syncthreads();
+  if (threadIdx.x < n_experts) {
+    int total = 0;
+#pragma unroll
+    for (int w = 0; w < kSortWaves; ++w) total += cnt[w][threadIdx.x];
+    block_counts[static_cast<int64_t>(blockIdx.x) * n_experts + threadIdx.x] = total;
+  }
+}
+
+// One block: thread e turns block_counts[:, e] into an exclusive prefix over blocks,
+// then thread 0 builds counts / offsets.
+__global__ __launch_bounds__(64) void offsets_kernel(int32_t *__restrict__ block_counts,
+                                                     int64_t n_blocks, int n_experts,
+                                                     int32_t *__restrict__ counts,
+                                                     int32_t *__restrict__ offsets) {
+  __shared__ int total[64];
+  const int e = threadIdx.x;
+  if (e < n_experts) {
+    int run = 0;
+    for (int64_t b = 0; b < n_blocks; ++b) {
+      const int c = block_counts[b * n_experts + e];
+      block_counts[b * n_experts + e] = run;
+      run += c;
+    }
+    total[e] = run;
+    counts[e] = run;
+  }
+  __syncthreads();
+  if (e == 0) {
+    int run = 0;
+    for (int i = 0; i < n_experts; ++i) { offsets[i] = run; run += total[i]; }
+    offsets[n_experts] = run;
+  }
+}
+
+__global__ __launch_bounds__(kSortBlock) void scatter_kernel(
+    const int32_t *__restrict__ expert_idx, int64_t n_slots, int n_experts, int top_k,
+    const int32_t *__restrict__ block_base, const int32_t *__restrict__ offsets,
+    int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm, int32_t *__restrict__ tok_of_pos) {
+  __shared__ int cnt[kSortWaves][64];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int64_t s = static_cast<int64_t>(blockIdx.x) * kSortBlock + threadIdx.x;
+  const int key = (s < n_slots) ? expert_idx[s] : -1;
+  const unsigned long long same = match_expert(key, n_experts, lane, cnt[wave]);
+  __syncthreads();
+  if (s >= n_slots) return;
+  const unsigned long long below = same & ((1ull << lane) - 1ull);
+  int pos = offsets[key] + block_base[static_cast<int64_t>(blockIdx.x) * n_experts + key] +
+            __popcll(below);
+  for (int w = 0; w < wave; ++w) pos += cnt[w][key];
+  inv_perm[s] = pos;
+  perm[pos] = static_cast<int32_t>(s);
+  tok_of_pos[pos] = static_cast<int32_t>(s / top_k);
+}
+
+template <typename T>
+hipError_t route_dispatch(const void *x, const void *w_router, const float *b_router,
+                          int64_t n_tokens, int d_model, int n_experts, int top_k, int gate_mode,
+                          int32_t *expert_idx, float *gate, float *logits, hipStream_t s) {
+  const T *xp = static_cast<const T *>(x);
+  const T *wp = static_cast<const T *>(w_router);
+#define ROM_ROUTE_LAUNCH(EMAX, TOK)                                                              \
+  do {                                                                                           \
+    const int64_t waves = ceil_div(n_tokens, TOK);                                               \
+    const int64_t blocks = ceil_div(waves, 4);                                                   \
+    hipLaunchKernelGGL((route_topk_kernel<T, EMAX, TOK>), dim3(static_cast<unsigned>(blocks)),   \
+                       dim3(256), 0, s, xp, wp, b_router, n_tokens, d_model, n_experts, top_k,   \
+                       gate_mode, expert_idx, gate, logits);                                     \
+  } while (0)
+  if (n_experts <= 8) ROM_ROUTE_LAUNCH(8, 4);
+  else if (n_experts <= 16) ROM_ROUTE_LAUNCH(16, 2);
+  else if (n_experts <= 32) ROM_ROUTE_LAUNCH(32, 1);
+  else ROM_ROUTE_LAUNCH(64, 1);
+#undef ROM_ROUTE_LAUNCH
+  return hipGetLastError();
+}
+
+}  // namespace
+
+int64_t route_blocks(int64_t n_slots) { return ceil_div(n_slots, kSortBlock); }
+
+hipError_t launch_route_topk(int dtype, const void *x, const void *w_router, const float *b_router,
+                             int64_t n_tokens, int d_model, int n_experts, int top_k, int gate_mode,
+                             int32_t *expert_idx, float *gate, float *logits, hipStream_t s) {
+  if (dtype == ROM_DTYPE_BF16)
+    return route_dispatch<bf16_t>(x, w_router, b_router, n_tokens, d_model, n_experts, top_k,
+                                  gate_mode, expert_idx, gate, logits, s);
+  return route_dispatch<float>(x, w_router, b_router, n_tokens, d_model, n_experts, top_k, gate_mode,
+                               expert_idx, gate, logits, s);
+}
+
+hipError_t launch_permutation(const int32_t *expert_idx, int64_t n_slots, int n_experts, int top_k,
+                              int32_t *block_counts, int32_t *counts, int32_t *offsets,
+                              int32_t *perm, int32_t *inv_perm, int32_t *tok_of_pos, hipStream_t s) {
+  const int64_t blocks = route_blocks(n_slots);
+  hipLaunchKernelGGL(hist_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kSortBlock), 0, s,
+                     expert_idx, n_slots, n_experts, block_counts);
+  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(64), 0, s, block_counts, blocks, n_experts, counts,
+                     offsets);
+  hipLaunchKernelGGL(scatter_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kSortBlock), 0, s,
+                     expert_idx, n_slots, n_experts, top_k, block_counts, offsets, perm, inv_perm,
+                     tok_of_pos);
+  return hipGetLastError();
+}
+
+}  // namespace rom

@@ -1,0 +1,412 @@
+// Sequence-mixing and elementwise kernels of the RoM layer:
+//   causal depthwise conv + SiLU (Eq. (2)), selective scan with D skip and SiLU(z) gating
+//   (Eq. (5), (6)/(13)), the per-token sums over the K selected experts (Eq. (10)/(11)) and the
+//   gate-weighted combine (Eq. (12)).  All of this is bandwidth / plain-ALU work: no MFMA here.
+#include "rom_internal.h"
+
+namespace rom {
+
+namespace {
+
+// ------------------------------------------------------------------ small vector helpers
+template <typename T> struct Chunk;           // 16 bytes of T
+template <> struct Chunk<bf16_t> {
+  static constexpr int kElems = 8;
+  uint4 raw;
+  __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const uint4 *>(p); }
+  __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<uint4 *>(p) = raw; }
+  __device__ __forceinline__ float get(int i) const {
+    const unsigned int w = (&raw.x)[i >> 1];
+    return __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16));
+  }
+  __device__ __forceinline__ void set_pair(int i, float lo, float hi) {   // elements 2i, 2i+1
+    (&raw.x)[i] = static_cast<unsigned int>(f32_to_bf16(lo)) |
+                  (static_cast<unsigned int>(f32_to_bf16(hi)) << 16);
+  }
+};
+template <> struct Chunk<float> {
+  static constexpr int kElems = 4;
+  float4 raw;
+  __device__ __forceinline__ void load(const float *p) { raw = *reinterpret_cast<const float4 *>(p); }
+  __device__ __forceinline__ void store(float *p) const { *reinterpret_cast<float4 *>(p) = raw; }
+  __device__ __forceinline__ float get(int i) const { return (&raw.x)[i]; }
+  __device__ __forceinline__ void set_pair(int i, float lo, float hi) {
+    (&raw.x)[2 * i] = lo;
+    (&raw.x)[2 * i + 1] = hi;
+  }
+};
+
+__device__ __forceinline__ float softplus_f32(float v) {
+  // log(1 + exp(v)) without overflow; for v > 20 the correction is below fp32 resolution
+  return v > 20.0f ? v : log1pf(__expf(v));
+}
+
+// ------------------------------------------------------------------ sum over the K slots
+template <typename TS, typename TD>
+__global__ __launch_bounds__(256) void slot_sum_kernel(const TS *__restrict__ src, int64_t ld_src,
+                                                       TD *__restrict__ dst, int64_t ld_dst,
+                                                       const int32_t *__restrict__ inv_perm,
+                                                       int64_t n_tokens, int top_k, int n_cols,
+                                                       const float *__restrict__ bias, int softplus) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int pairs = n_cols / 2;
+  if (idx >= n_tokens * pairs) return;
+  const int64_t n = idx / pairs;
+  const int c = static_cast<int>(idx % pairs) * 2;
+  float a0 = 0.0f, a1 = 0.0f;
+  for (int k = 0; k < top_k; ++k) {
+    const int64_t row = inv_perm[n * top_k + k];
+    a0 += to_f32(src[row * ld_src + c]);
+    a1 += to_f32(src[row * ld_src + c + 1]);
+  }
+  if (bias) { a0 += bias[c]; a1 += bias[c + 1]; }
+  if (softplus) { a0 = softplus_f32(a0); a1 = softplus_f32(a1); }
+  dst[n * ld_dst + c] = from_f32<TD>(a0);
+  dst[n * ld_dst + c + 1] = from_f32<TD>(a1);
+}
+
+// xdbl rows (f32, R + 32 columns) -> dt_low (T) and bc (f32); sums the K slots when inv_perm is given
+template <typename T>
+__global__ __launch_bounds__(256) void split_xdbl_kernel(const float *__restrict__ xdbl,
+                                                         const int32_t *__restrict__ inv_perm,
+                                                         int top_k, int64_t n_tokens, int dt_rank,
+                                                         T *__restrict__ dt_low, float *__restrict__ bc) {
+  const int n_cols = dt_rank + 32;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (idx >= n_tokens * n_cols) return;
+  const int64_t n = idx / n_cols;
+  const int c = static_cast<int>(idx % n_cols);
+  float acc = 0.0f;
+  if (inv_perm) {
+    for (int k = 0; k < top_k; ++k) acc += xdbl[static_cast<int64_t>(inv_perm[n * top_k + k]) * n_cols + c];
+  } else {
+    acc = xdbl[n * n_cols + c];
+  }
+  if (c < dt_rank) dt_low[n * dt_rank + c] = from_f32<T>(acc);
+  else bc[n * 32 + (c - dt_rank)] = acc;
+}
+
+// ------------------------------------------------------------------ conv + SiLU, Eq. (2)
+// A thread owns one 16-byte group of channels and walks kConvRun consecutive time steps with the
+// last three inputs in registers, so every input row is read once (plus a 3-row halo per run).
+constexpr int kConvRun = 32;
+
+template <typename T>
+__global__ __launch_bounds__(256) void conv_silu_kernel(
+    const T *__restrict__ xz, int64_t ld_xz, const float *__restrict__ conv_w,
+    const float *__restrict__ conv_b, const float *__restrict__ state_in,
+    float *__restrict__ state_out, T *__restrict__ u, int64_t L, int d_inner) {
+  constexpr int V = Chunk<T>::kElems;
+  const int groups = d_inner / V;
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= groups) return;
+  const int c0 = g * V;
+  const int64_t b = blockIdx.z;
+  const int64_t t0 = static_cast<int64_t>(blockIdx.y) * kConvRun;
+  const int64_t t1 = (t0 + kConvRun < L) ? t0 + kConvRun : L;
+
+  float w[V][4], bias[V], h[3][V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) {
+    const float4 wv = *reinterpret_cast<const float4 *>(conv_w + static_cast<int64_t>(c0 + i) * 4);
+    w[i][0] = wv.x; w[i][1] = wv.y; w[i][2] = wv.z; w[i][3] = wv.w;
+    bias[i] = conv_b ? conv_b[c0 + i] : 0.0f;
+  }
+  const T *xrow = xz + b * L * ld_xz + c0;
+  // history: inputs at t0-3, t0-2, t0-1
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    const int64_t t = t0 - 3 + j;
+    if (t >= 0) {
+      Chunk<T> ch;
+      ch.load(xrow + t * ld_xz);
+#pragma unroll
+      for (int i = 0; i < V; ++i) h[j][i] = ch.get(i);
+    } else {
+#pragma unroll
+      for (int i = 0; i < V; ++i)   // t = -3..-1 -> state slot 3 + t
+        h[j][i] = state_in ? state_in[(b * d_inner + c0 + i) * 3 + (3 + t)] : 0.0f;
+    }
+  }
+  T *urow = u + b * L * d_inner + c0;
+  for (int64_t t = t0; t < t1; ++t) {
+    Chunk<T> ch, out;
+    ch.load(xrow + t * ld_xz);
+    float r[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      const float cur = ch.get(i);
+      const float c = bias[i] + w[i][0] * h[0][i] + w[i][1] * h[1][i] + w[i][2] * h[2][i] + w[i][3] * cur;
+      h[0][i] = h[1][i]; h[1][i] = h[2][i]; h[2][i] = cur;
+      r[i] = silu_f32(c);
+    }
+#pragma unroll
+    for (int i = 0; i < V / 2; ++i) out.set_pair(i, r[2 * i], r[2 * i + 1]);
+    out.store(urow + t * d_inner);
+  }
+  if (state_out && t1 == L) {
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+#pragma unroll
+      for (int i = 0; i < V; ++i) state_out[(b * d_inner + c0 + i) * 3 + j] = h[j][i];
+  }
+}
+
+// ------------------------------------------------------------------ selective scan, Eq. (5)
+// Lane = (channel, state): 16 lanes share a channel, a 256-thread block owns 16 channels of one
+// sequence and walks the whole sequence once, the 16 states of every channel living in registers
+// (one per lane).  Inputs come through LDS in tiles of kScanTile steps; inside a tile, 16 steps at
+// a time: lane n of a channel fetches dt and u of step n, the per-step values are handed round
+// with row broadcasts, and the 16 products C_n*h_n of 16 steps are summed with a transposing
+// butterfly so that lane n ends up with y of step n and does that step's D skip and SiLU(z) gate.
+constexpr int kScanTile = 64;
+constexpr int kScanCh = 16;
+
+template <int CTRL> __device__ __forceinline__ float dpp(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+constexpr int kDppQuadXor1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kDppQuadRev = 0x1B;       // quad_perm [3,2,1,0]
+constexpr int kDppHalfMirror = 0x141;   // lane i <-> 7 - i inside each 8
+constexpr int kDppRowMirror = 0x140;    // lane i <-> 15 - i inside each 16
+constexpr int kDppRowBcast0 = 0x150;    // row_newbcast:0 (+j for lane j of the row)
+
+struct ScanSmem {
+  float dt[kScanTile][kScanCh];
+  float u[kScanTile][kScanCh];
+  float z[kScanTile][kScanCh];
+  float bc[32][kScanTile + 4];          // transposed: [B_0..B_15, C_0..C_15][step]
+  float g[kScanTile][kScanCh];
+};
+
+template <int J> struct StepSeq {
+  __device__ static __forceinline__ void run(float dt_r, float dtu_r, float a2, const float *bv,
+                                             const float *cv, float &h, float *p) {
+    StepSeq<J - 1>::run(dt_r, dtu_r, a2, bv, cv, h, p);
+    const float dtj = dpp<kDppRowBcast0 + J>(dt_r);
+    const float dtuj = dpp<kDppRowBcast0 + J>(dtu_r);
+    const float da = fast_exp2(dtj * a2);
+    h = fmaf(da, h, dtuj * bv[J]);
+    p[J] = h * cv[J];
+  }
+};
+template <> struct StepSeq<-1> {
+  __device__ static __forceinline__ void run(float, float, float, const float *, const float *,
+                                             float &, float *) {}
+};
+
+// Sum p[j] over the 16 lanes of a row for every j; lane i returns the total of p[i].
+__device__ __forceinline__ float transpose_reduce16(const float *p, int n) {
+  float a[8], b[4], c[2];
+  const bool hi8 = (n & 8) != 0, hi4 = (n & 4) != 0, hi2 = (n & 2) != 0, hi1 = (n & 1) != 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float lo = p[j] + dpp<kDppRowMirror>(p[j]);
+    const float hi = p[j + 8] + dpp<kDppRowMirror>(p[j + 8]);
+    a[j] = hi8 ? hi : lo;
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float lo = a[j] + dpp<kDppHalfMirror>(a[j]);
+    const float hi = a[j + 4] + dpp<kDppHalfMirror>(a[j + 4]);
+    b[j] = hi4 ? hi : lo;
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const float lo = b[j] + dpp<kDppQuadRev>(b[j]);
+    const float hi = b[j + 2] + dpp<kDppQuadRev>(b[j + 2]);
+    c[j] = hi2 ? hi : lo;
+  }
+  const float lo = c[0] + dpp<kDppQuadXor1>(c[0]);
+  const float hi = c[1] + dpp<kDppQuadXor1>(c[1]);
+  return hi1 ? hi : lo;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void scan_gate_kernel(
+    const T *__restrict__ u, const T *__restrict__ dt, const float *__restrict__ bc,
+    const T *__restrict__ z, int64_t ld_z, const float *__restrict__ A_log,
+    const float *__restrict__ D, const float *__restrict__ h_in, float *__restrict__ h_out,
+    T *__restrict__ g, int64_t L, int d_inner) {
+  __shared__ ScanSmem sm;
+  const int tid = threadIdx.x;
+  const int n = tid & 15;            // state index
+  const int cl = tid >> 4;           // channel inside the block
+  // consecutive workgroups land on different XCDs (round-robin over 8): give each XCD a
+  // contiguous run of channel groups so that neighbours in memory share an L2.
+  const int n_groups = d_inner / kScanCh;
+  int grp = blockIdx.x;
+  if (n_groups % 8 == 0) grp = (blockIdx.x % 8) * (n_groups / 8) + blockIdx.x / 8;
+  const int c0 = grp * kScanCh;
+  const int ch = c0 + cl;
+  const int64_t b = blockIdx.y;
+
+  const float a2 = -__expf(A_log[static_cast<int64_t>(ch) * 16 + n]) * 1.44269504088896341f;
+  const float d_skip = D[ch];
+  float h = h_in ? h_in[(b * d_inner + ch) * 16 + n] : 0.0f;
+
+  const T *u_b = u + b * L * d_inner + c0;
+  const T *dt_b = dt + b * L * d_inner + c0;
+  const T *z_b = z + b * L * ld_z + c0;
+  const float *bc_b = bc + b * L * 32;
+  T *g_b = g + b * L * d_inner + c0;
+
+  // staging roles: thread -> (row, 4-channel quarter) of the dt/u/z tiles, (row, 8-float part) of bc
+  const int s_row = tid >> 2, s_q = (tid & 3) * 4;
+
+  for (int64_t t0 = 0; t0 < L; t0 += kScanTile) {
+    __syncthreads();                 // previous tile fully consumed
+    {
+      const int64_t t = t0 + s_row;
+      const bool ok = t < L;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        sm.dt[s_row][s_q + i] = ok ? to_f32(dt_b[t * d_inner + s_q + i]) : 0.0f;
+        sm.u[s_row][s_q + i] = ok ? to_f32(u_b[t * d_inner + s_q + i]) : 0.0f;
+        sm.z[s_row][s_q + i] = ok ? to_f32(z_b[t * ld_z + s_q + i]) : 0.0f;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int col = (tid & 3) * 8 + i;
+        sm.bc[col][s_row] = ok ? bc_b[t * 32 + col] : 0.0f;
+      }
+    }
+    __syncthreads();
+
+#pragma unroll 1
+    for (int s0 = 0; s0 < kScanTile; s0 += 16) {
+      const float dt_r = sm.dt[s0 + n][cl];
+      const float u_r = sm.u[s0 + n][cl];
+      const float dtu_r = dt_r * u_r;
+      float bv[16], cv[16], p[16];
+#pragma unroll
+      for (int j = 0; j < 16; j += 4) {
+        const float4 b4 = *reinterpret_cast<const float4 *>(&sm.bc[n][s0 + j]);
+        const float4 c4 = *reinterpret_cast<const float4 *>(&sm.bc[16 + n][s0 + j]);
+        bv[j] = b4.x; bv[j + 1] = b4.y; bv[j + 2] = b4.z; bv[j + 3] = b4.w;
+        cv[j] = c4.x; cv[j + 1] = c4.y; cv[j + 2] = c4.z; cv[j + 3] = c4.w;
+      }
+      StepSeq<15>::run(dt_r, dtu_r, a2, bv, cv, h, p);
+      const float y = transpose_reduce16(p, n) + d_skip * u_r;
+      sm.g[s0 + n][cl] = y * silu_f32(sm.z[s0 + n][cl]);
+    }
+    __syncthreads();
+    {
+      const int64_t t = t0 + s_row;
+      if (t < L) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) g_b[t * d_inner + s_q + i] = from_f32<T>(sm.g[s_row][s_q + i]);
+      }
+    }
+  }
+  if (h_out) h_out[(b * d_inner + ch) * 16 + n] = h;
+}
+
+// ------------------------------------------------------------------ combine, Eq. (12)
+template <typename T>
+__global__ __launch_bounds__(256) void combine_kernel(const T *__restrict__ op,
+                                                      const int32_t *__restrict__ inv_perm,
+                                                      const float *__restrict__ gate,
+                                                      T *__restrict__ out, int64_t n_tokens,
+                                                      int top_k, int d_model) {
+  constexpr int V = Chunk<T>::kElems;
+  const int groups = d_model / V;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (idx >= n_tokens * groups) return;
+  const int64_t n = idx / groups;
+  const int c0 = static_cast<int>(idx % groups) * V;
+  float acc[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+  for (int k = 0; k < top_k; ++k) {
+    const int64_t row = inv_perm[n * top_k + k];
+    const float gk = gate[n * top_k + k];
+    Chunk<T> ch;
+    ch.load(op + row * d_model + c0);
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = fmaf(gk, ch.get(i), acc[i]);
+  }
+  Chunk<T> o;
+#pragma unroll
+  for (int i = 0; i < V / 2; ++i) o.set_pair(i, acc[2 * i], acc[2 * i + 1]);
+  o.store(out + n * d_model + c0);
+}
+
+inline dim3 grid1d(int64_t work, int block) { return dim3(static_cast<unsigned>(ceil_div(work, block))); }
+
+}  // namespace
+
+hipError_t launch_slot_sum(int src_is_f32, int dst_is_f32, const void *src, int64_t ld_src, void *dst,
+                           int64_t ld_dst, const int32_t *inv_perm, int64_t n_tokens, int top_k,
+                           int n_cols, const float *bias, int softplus, hipStream_t s) {
+  const dim3 grid = grid1d(n_tokens * (n_cols / 2), 256);
+#define ROM_SS(TS, TD)                                                                            \
+  hipLaunchKernelGGL((slot_sum_kernel<TS, TD>), grid, dim3(256), 0, s, static_cast<const TS *>(src), \
+                     ld_src, static_cast<TD *>(dst), ld_dst, inv_perm, n_tokens, top_k, n_cols,    \
+                     bias, softplus)
+  if (src_is_f32 && dst_is_f32) ROM_SS(float, float);
+  else if (src_is_f32) ROM_SS(float, bf16_t);
+  else if (dst_is_f32) ROM_SS(bf16_t, float);
+  else ROM_SS(bf16_t, bf16_t);
+#undef ROM_SS
+  return hipGetLastError();
+}
+
+hipError_t launch_split_xdbl(int dtype, const float *xdbl, const int32_t *inv_perm, int top_k,
+                             int64_t n_tokens, int dt_rank, void *dt_low, float *bc, hipStream_t s) {
+  const dim3 grid = grid1d(n_tokens * (dt_rank + 32), 256);
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL(split_xdbl_kernel<bf16_t>, grid, dim3(256), 0, s, xdbl, inv_perm, top_k,
+                       n_tokens, dt_rank, static_cast<bf16_t *>(dt_low), bc);
+  else
+    hipLaunchKernelGGL(split_xdbl_kernel<float>, grid, dim3(256), 0, s, xdbl, inv_perm, top_k,
+                       n_tokens, dt_rank, static_cast<float *>(dt_low), bc);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_silu(int dtype, const void *xz, int64_t ld_xz, const float *conv_w,
+                            const float *conv_b, const float *state_in, float *state_out, void *u,
+                            int64_t B, int64_t L, int d_inner, hipStream_t s) {
+  const int V = dtype == ROM_DTYPE_BF16 ? 8 : 4;
+  const int groups = d_inner / V;
+  const dim3 grid(static_cast<unsigned>(ceil_div(groups, 256)),
+                  static_cast<unsigned>(ceil_div(L, kConvRun)), static_cast<unsigned>(B));
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL(conv_silu_kernel<bf16_t>, grid, dim3(256), 0, s,
+                       static_cast<const bf16_t *>(xz), ld_xz, conv_w, conv_b, state_in, state_out,
+                       static_cast<bf16_t *>(u), L, d_inner);
+  else
+    hipLaunchKernelGGL(conv_silu_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(xz),
+                       ld_xz, conv_w, conv_b, state_in, state_out, static_cast<float *>(u), L, d_inner);
+  return hipGetLastError();
+}
+
+hipError_t launch_scan_gate(int dtype, const void *u, const void *dt, const float *bc, const void *z,
+                            int64_t ld_z, const float *A_log, const float *D, const float *h_in,
+                            float *h_out, void *g, int64_t B, int64_t L, int d_inner, hipStream_t s) {
+  const dim3 grid(static_cast<unsigned>(d_inner / kScanCh), static_cast<unsigned>(B));
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL(scan_gate_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(u),
+                       static_cast<const bf16_t *>(dt), bc, static_cast<const bf16_t *>(z), ld_z, A_log,
+                       D, h_in, h_out, static_cast<bf16_t *>(g), L, d_inner);
+  else
+    hipLaunchKernelGGL(scan_gate_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(u),
+                       static_cast<const float *>(dt), bc, static_cast<const float *>(z), ld_z, A_log, D,
+                       h_in, h_out, static_cast<float *>(g), L, d_inner);
+  return hipGetLastError();
+}
+
+hipError_t launch_combine(int dtype, const void *op, const int32_t *inv_perm, const float *gate,
+                          void *out, int64_t n_tokens, int top_k, int d_model, hipStream_t s) {
+  const int V = dtype == ROM_DTYPE_BF16 ? 8 : 4;
+  const dim3 grid = grid1d(n_tokens * (d_model / V), 256);
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL(combine_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(op),
+                       inv_perm, gate, static_cast<bf16_t *>(out), n_tokens, top_k, d_model);
+  else
+    hipLaunchKernelGGL(combine_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(op),
+                       inv_perm, gate, static_cast<float *>(out), n_tokens, top_k, d_model);
+  return hipGetLastError();
+}
+
+}  // namespace rom

@@ -1,0 +1,113 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+include/rom.h declares, and its argument validation / workspace planning behave as documented."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2506_18145_amd import binding
+    if not os.path.exists(binding._LIB_PATH):
+        from paper_2506_18145_amd.build import build_library
+        build_library()
+    return binding.load_library()
+
+
+def _dims(**kw):
+    from paper_2506_18145_amd.binding import RomDims
+    base = dict(d_model=64, d_inner=128, d_state=16, d_conv=4, dt_rank=8, n_experts=4, top_k=1,
+                n_experts_xdt=4, dtype=0, gate_mode=0)
+    base.update(kw)
+    return RomDims(**base)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "rom.h")).read()
+    names = re.findall(r"ROM_API\s+[\w\s\*]+?\b(rom_\w+)\s*\(", header)
+    assert len(names) >= 9
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_struct_sizes_match_header():
+    from paper_2506_18145_amd import binding
+    assert ctypes.sizeof(binding.RomDims) == 40
+    assert ctypes.sizeof(binding._RomWeights) == 11 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(binding._RomWsLayout) == 14 * ctypes.sizeof(ctypes.c_size_t)
+
+
+def test_workspace_bytes_and_layout(lib):
+    from paper_2506_18145_amd import binding
+    d = _dims()
+    small = binding.rom_workspace_bytes(d, 1, 64)
+    big = binding.rom_workspace_bytes(d, 2, 64)
+    assert 0 < small < big
+    lay = binding.rom_workspace_layout(d, 1, 64)
+    assert lay["total_bytes"] == small
+    offs = [lay[k] for k in ("expert_idx", "gate", "counts", "offsets", "perm", "inv_perm", "logits",
+                             "xz", "u", "dt_low", "bc", "dt", "g")]
+    assert offs == sorted(offs) and len(set(offs)) == len(offs)
+    assert all(o % 256 == 0 and o < small for o in offs)
+    # xz holds N * 2*d_inner fp32 values before u starts
+    assert lay["u"] - lay["xz"] >= 64 * 2 * 128 * 4
+
+
+def test_invalid_dims_are_rejected_before_any_launch(lib):
+    from paper_2506_18145_amd import binding
+    assert binding.rom_workspace_bytes(_dims(d_state=8), 1, 8) == 0          # unsupported
+    assert binding.rom_workspace_bytes(_dims(top_k=5), 1, 8) == 0            # K > E
+    assert binding.rom_workspace_bytes(_dims(dtype=7), 1, 8) == 0
+    lay = binding._RomWsLayout()
+    assert lib.rom_workspace_layout(ctypes.byref(_dims(d_conv=3)), 1, 8, ctypes.byref(lay)) == -3
+    assert lib.rom_workspace_layout(ctypes.byref(_dims(top_k=0)), 1, 8, ctypes.byref(lay)) == -1
+    assert lib.rom_workspace_layout(ctypes.byref(_dims(n_experts_xdt=2)), 1, 8, ctypes.byref(lay)) == -1
+    w = binding._RomWeights()                                                # all NULL
+    d = _dims()
+    # NULL weights / tensors: refused with ROM_E_INVAL, nothing is launched (no GPU here)
+    assert lib.rom_layer_forward(ctypes.byref(d), ctypes.byref(w), None, 1, 8, None, None, None, None,
+                                 None, None, 0, None) == -1
+    assert lib.rom_route(ctypes.byref(d), ctypes.byref(w), None, 8, None, None, None, None, None, None,
+                         None, None, 0, None) == -1
+    assert lib.rom_step(ctypes.byref(d), ctypes.byref(w), None, 4, None, None, None, None, 0, None) == -1
+    assert lib.rom_layer_forward(None, ctypes.byref(w), None, 1, 8, None, None, None, None, None, None,
+                                 0, None) == -1
+
+
+def test_error_strings_and_stage_names(lib):
+    assert lib.rom_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4):
+        assert len(lib.rom_strerror(code)) > 5
+    from paper_2506_18145_amd.binding import STAGE_NAMES
+    assert tuple(lib.rom_stage_name(i).decode() for i in range(len(STAGE_NAMES))) == STAGE_NAMES
+
+
+def test_empty_input_is_a_successful_noop(lib):
+    """B == 0 or L == 0 returns ROM_OK without touching any pointer (so it is safe with no GPU)."""
+    from paper_2506_18145_amd import binding
+    d = _dims()
+    buf = ctypes.create_string_buffer(4096 + 256)
+    addr = (ctypes.addressof(buf) + 255) // 256 * 256
+    w = binding._RomWeights(*([addr] * 11))
+    assert lib.rom_layer_forward(ctypes.byref(d), ctypes.byref(w), addr, 0, 8, None, None, addr, None,
+                                 None, addr, 4096, None) == 0
+    assert lib.rom_layer_forward(ctypes.byref(d), ctypes.byref(w), addr, 2, 0, None, None, addr, None,
+                                 None, addr, 4096, None) == 0
+    assert lib.rom_route(ctypes.byref(d), ctypes.byref(w), addr, 0, addr, addr, addr, addr, addr, addr,
+                         None, addr, 4096, None) == 0
+    assert lib.rom_step(ctypes.byref(d), ctypes.byref(w), addr, 0, None, None, addr, addr, 4096, None) == 0
+
+
+def test_binding_refuses_to_run_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    from paper_2506_18145_amd import RomError, RomLayer
+    from rom_synth import get_config, make_weights
+    cfg = get_config("cfg0")
+    with pytest.raises(RomError):
+        RomLayer(cfg, make_weights(cfg))
