@@ -51,8 +51,9 @@ extern "C" {
 #define ROM_DTYPE_BF16 1        /* bf16 weights/activations, fp32 accumulation and scan state */
 
 /* Shape of one layer.  Supported: d_state == 16, d_conv == 4, 1 <= top_k <= n_experts <= 64,
- * top_k <= 8, d_inner % 16 == 0, d_model % 8 == 0, dt_rank % 8 == 0,
- * n_experts_xdt in {1, n_experts}.  Anything else returns ROM_E_UNSUPPORTED / ROM_E_INVAL. */
+ * top_k <= 8, d_inner % 16 == 0, d_model % 8 == 0, n_experts_xdt in {1, n_experts}.  Anything else
+ * returns ROM_E_UNSUPPORTED / ROM_E_INVAL.  (bf16 projections whose inner dimension is not a
+ * multiple of 8 run on the plain FMA kernel instead of the MFMA one.) */
 typedef struct rom_dims {
   int32_t d_model;        /* D_m                                             */
   int32_t d_inner;        /* D_e (paper: 2 D_m)                              */

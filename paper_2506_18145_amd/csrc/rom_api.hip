@@ -25,7 +25,7 @@ int check_dims(const rom_dims *d) {
   if (d->n_experts_xdt != 1 && d->n_experts_xdt != d->n_experts) return ROM_E_INVAL;
   if (d->d_state != 16 || d->d_conv != 4) return ROM_E_UNSUPPORTED;
   if (d->n_experts > 64 || d->top_k > 8) return ROM_E_UNSUPPORTED;
-  if (d->d_inner % 16 != 0 || d->d_model % 8 != 0 || d->dt_rank % 8 != 0) return ROM_E_UNSUPPORTED;
+  if (d->d_inner % 16 != 0 || d->d_model % 8 != 0) return ROM_E_UNSUPPORTED;
   return ROM_OK;
 }
 
