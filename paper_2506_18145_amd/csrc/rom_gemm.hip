@@ -19,6 +19,15 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 
 __device__ __forceinline__ float softplus_f32(float v) { return v > 20.0f ? v : log1pf(__expf(v)); }
+// branch-free softplus for the bf16 epilogue: log(1 + e) by its series where 1 + e would round
+// (relative error < 1e-5, far below the bf16 rounding of the stored result)
+__device__ __forceinline__ float softplus_fast(float v) {
+  const float e = __expf(fminf(v, 20.0f));
+  const float series = e * (1.0f - e * (0.5f - e * 0.333333333f));
+  const float full = __logf(1.0f + e);
+  const float r = e < 0.03f ? series : full;
+  return v > 20.0f ? v : r;
+}
 
 struct TileCoord {
   int group;
@@ -69,6 +78,9 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmArgs &a, int BM, int 
   return tc;
 }
 
+// epilogue variants of the MFMA kernel (compile-time, so the store loop has no branches)
+enum { kEpiPlain = 0, kEpiBiasSoftplus = 1, kEpiRowScale = 2, kEpiPlainF32 = 3 };
+
 __device__ __forceinline__ void store_out(const GemmArgs &a, int64_t crow, int col, float v) {
   if (a.bias) v += a.bias[col];
   if (a.softplus) v = softplus_f32(v);
@@ -83,7 +95,7 @@ __device__ __forceinline__ void store_out(const GemmArgs &a, int64_t crow, int c
 constexpr int kBK = 64;                 // K slab, 8 chunks of 8 bf16 (16 bytes) per row
 constexpr int kRowChunks = kBK / 8;
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmArgs a) {
   constexpr int NT = WM * WN * 64;
   constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
@@ -104,37 +116,49 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
   const bf16_t *Ap = static_cast<const bf16_t *>(a.A);
   const bf16_t *Wp = static_cast<const bf16_t *>(a.W) + static_cast<int64_t>(tc.group) * a.N * a.K;
 
-  // global source of every 16-byte chunk this thread stages (row base offset or -1)
+  // global source of every 16-byte chunk this thread stages.  Rows past the end of the tile are
+  // redirected to its first row (their results are never stored), so the loads need no branch;
+  // a K tail is zero-filled by a select.
   int64_t a_src[A_CH], b_src[B_CH];
 #pragma unroll
   for (int i = 0; i < A_CH; ++i) {
     const int q = tid + i * NT, r = q / kRowChunks;
-    const int64_t p = tc.row0 + r;
-    a_src[i] = -1;
-    if (p < tc.row_end) a_src[i] = static_cast<int64_t>(a.a_rows ? a.a_rows[p] : p) * a.lda;
+    int64_t p = tc.row0 + r;
+    if (p >= tc.row_end) p = tc.row0;
+    a_src[i] = static_cast<int64_t>(a.a_rows ? a.a_rows[p] : p) * a.lda;
   }
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) {
     const int q = tid + i * NT, r = q / kRowChunks;
-    b_src[i] = (tc.n0 + r < a.N) ? static_cast<int64_t>(tc.n0 + r) * a.K : -1;
+    const int n = (tc.n0 + r < a.N) ? tc.n0 + r : a.N - 1;
+    b_src[i] = static_cast<int64_t>(n) * a.K;
   }
+  const int k_chunk = (tid % kRowChunks) * 8;
+  const int k_last = a.K - 8;
 
   uint4 ra[A_CH], rb[B_CH];
+  // full slab: every chunk lies inside K, plain unconditional loads
+  auto load_full = [&](int k0) {
+    const int k = k0 + k_chunk;
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) ra[i] = *reinterpret_cast<const uint4 *>(Ap + a_src[i] + k);
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const uint4 *>(Wp + b_src[i] + k);
+  };
+  // last slab when K is not a multiple of the slab: chunks past K are zero
+  auto load_tail = [&](int k0) {
+    const int k = k0 + k_chunk;
+    const bool k_ok = k <= k_last;
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i)
+      ra[i] = k_ok ? *reinterpret_cast<const uint4 *>(Ap + a_src[i] + k) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i)
+      rb[i] = k_ok ? *reinterpret_cast<const uint4 *>(Wp + b_src[i] + k) : make_uint4(0, 0, 0, 0);
+  };
   auto load_global = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-      const int c = (tid + i * NT) % kRowChunks;
-      const int k = k0 + c * 8;
-      ra[i] = (a_src[i] >= 0 && k < a.K) ? *reinterpret_cast<const uint4 *>(Ap + a_src[i] + k)
-                                         : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-      const int c = (tid + i * NT) % kRowChunks;
-      const int k = k0 + c * 8;
-      rb[i] = (b_src[i] >= 0 && k < a.K) ? *reinterpret_cast<const uint4 *>(Wp + b_src[i] + k)
-                                         : make_uint4(0, 0, 0, 0);
-    }
+    if (k0 + kBK <= a.K) load_full(k0);
+    else load_tail(k0);
   };
   auto store_lds = [&](int buf) {
 #pragma unroll
@@ -158,55 +182,108 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
   const int KT = (a.K + kBK - 1) / kBK;
+  const int frag_row = lane & 31, frag_half = lane >> 5;
+  // LDS chunk index of this lane's fragment for 16-wide K step kk: row * 8 + ((2 kk + half) ^ (row & 7));
+  // the wave / tile row offsets are multiples of 8, so the swizzle term depends on the lane only.
+  const int a_base = (wm * WTM + frag_row) * kRowChunks, b_base = (wn * WTN + frag_row) * kRowChunks;
+  const int swz = frag_row & 7;
+
+  bf16x8_t fa[2][TM], fb[2][TN];
+  auto load_frags = [&](int buf, int kk, bf16x8_t(&af)[TM], bf16x8_t(&bfr)[TN]) {
+    const int c = (kk * 2 + frag_half) ^ swz;
+    const uint4 *Ab = As + buf * BM * kRowChunks + a_base + c;
+    const uint4 *Bb = Bs + buf * BN * kRowChunks + b_base + c;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const uint4 v = Ab[i * 32 * kRowChunks];
+      af[i] = *reinterpret_cast<const bf16x8_t *>(&v);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const uint4 v = Bb[j * 32 * kRowChunks];
+      bfr[j] = *reinterpret_cast<const bf16x8_t *>(&v);
+    }
+  };
+  auto mma = [&](const bf16x8_t(&af)[TM], const bf16x8_t(&bfr)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+  };
+  // ask the scheduler to spread the next step's LDS fragment reads between this step's MFMAs
+  auto interleave_reads = [&]() {
+#pragma unroll
+    for (int i = 0; i < TM + TN; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                       // one DS read
+      __builtin_amdgcn_sched_group_barrier(0x008, (TM * TN) / (TM + TN), 0);   // a share of the MFMAs
+    }
+  };
+
   load_global(0);
   store_lds(0);
   __syncthreads();
+  load_frags(0, 0, fa[0], fb[0]);
 
-  const int frag_row = lane & 31, frag_half = lane >> 5;
   for (int kt = 0; kt < KT; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < KT) load_global((kt + 1) * kBK);
-    const uint4 *Ab = As + cur * BM * kRowChunks;
-    const uint4 *Bb = Bs + cur * BN * kRowChunks;
-#pragma unroll
-    for (int kk = 0; kk < kBK / 16; ++kk) {
-      const int c = kk * 2 + frag_half;
-      bf16x8_t af[TM], bfr[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const int r = wm * WTM + i * 32 + frag_row;
-        const uint4 v = Ab[r * kRowChunks + (c ^ (r & 7))];
-        af[i] = *reinterpret_cast<const bf16x8_t *>(&v);
-      }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int r = wn * WTN + j * 32 + frag_row;
-        const uint4 v = Bb[r * kRowChunks + (c ^ (r & 7))];
-        bfr[j] = *reinterpret_cast<const bf16x8_t *>(&v);
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) store_lds(cur ^ 1);
+    const bool has_next = kt + 1 < KT;
+    if (has_next) load_global((kt + 1) * kBK);        // lands while this slab is multiplied
+    load_frags(cur, 1, fa[1], fb[1]);
+    mma(fa[0], fb[0]);
+    interleave_reads();
+    load_frags(cur, 2, fa[0], fb[0]);
+    mma(fa[1], fb[1]);
+    interleave_reads();
+    load_frags(cur, 3, fa[1], fb[1]);
+    mma(fa[0], fb[0]);
+    interleave_reads();
+    // every fragment of this slab is in registers: stage the next slab, then overlap the
+    // fetch of its first fragments with the last 16-wide step of this one
+    if (has_next) store_lds(cur ^ 1);
     __syncthreads();
+    if (has_next) load_frags(cur ^ 1, 0, fa[0], fb[0]);
+    mma(fa[1], fb[1]);
   }
 
-  // epilogue: accumulator element v of a 32x32 tile sits at row 8*(v/4) + 4*(lane/32) + v%4,
-  // column lane%32
+  // epilogue.  The weight fragment is the MFMA's row operand, so a lane holds, for ONE output row
+  // (tile row lane%32), the output columns 8*q + 4*(lane/32) + r of each 32-wide tile in
+  // accumulator element 4*q + r: four consecutive columns per q, stored as one 8/16-byte write.
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
+    const int64_t p = tc.row0 + wm * WTM + i * 32 + frag_row;
+    const bool row_ok = p < tc.row_end;
+    const int64_t crow = row_ok ? (a.c_rows ? a.c_rows[p] : p) : 0;
+    float scale = 1.0f;
+    if (EPI == kEpiRowScale) scale = row_ok ? a.row_scale[crow] : 0.0f;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int64_t p = tc.row0 + wm * WTM + i * 32 + 8 * (v / 4) + 4 * frag_half + (v % 4);
-      if (p >= tc.row_end) continue;
-      const int64_t crow = a.c_rows ? a.c_rows[p] : p;
+    for (int j = 0; j < TN; ++j) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col = tc.n0 + wn * WTN + j * 32 + frag_row;
-        if (col < a.N) store_out(a, crow, col, acc[i][j][v]);
+      for (int q = 0; q < 4; ++q) {
+        const int col = tc.n0 + wn * WTN + j * 32 + q * 8 + frag_half * 4;
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
+        if (row_ok && col < a.N) {
+          if (EPI == kEpiBiasSoftplus) {
+            const float4 b4 = *reinterpret_cast<const float4 *>(a.bias + col);
+            v[0] = softplus_fast(v[0] + b4.x); v[1] = softplus_fast(v[1] + b4.y);
+            v[2] = softplus_fast(v[2] + b4.z); v[3] = softplus_fast(v[3] + b4.w);
+          }
+          if (EPI == kEpiRowScale) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] *= scale;
+          }
+          if (EPI == kEpiPlainF32) {
+            *reinterpret_cast<float4 *>(static_cast<float *>(a.C) + crow * a.ldc + col) =
+                make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+            uint2 pk;
+            pk.x = static_cast<unsigned int>(f32_to_bf16(v[0])) | (static_cast<unsigned int>(f32_to_bf16(v[1])) << 16);
+            pk.y = static_cast<unsigned int>(f32_to_bf16(v[2])) | (static_cast<unsigned int>(f32_to_bf16(v[3])) << 16);
+            *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(a.C) + crow * a.ldc + col) = pk;
+          }
+        }
       }
     }
   }
@@ -253,12 +330,12 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const GemmArgs a) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int64_t p = tc.row0 + ty * 4 + i;
-    if (p >= tc.row_end) continue;
-    const int64_t crow = a.c_rows ? a.c_rows[p] : p;
+    const bool row_ok = p < tc.row_end;
+    const int64_t crow = row_ok ? (a.c_rows ? a.c_rows[p] : p) : 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int col = tc.n0 + tx * 4 + j;
-      if (col < a.N) store_out(a, crow, col, acc[i][j]);
+      if (row_ok && col < a.N) store_out(a, crow, col, acc[i][j]);
     }
   }
 }
@@ -272,28 +349,40 @@ int grid_tiles(const GemmArgs &a, int BM, int BN) {
   return static_cast<int>(g);
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int EPI>
 hipError_t launch_mfma(const GemmArgs &a, hipStream_t s) {
   constexpr int kSmem = 2 * (BM + BN) * kRowChunks * 16;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_mfma_kernel<BM, BN, WM, WN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
+    hipError_t e = hipFuncSetAttribute(
+        reinterpret_cast<const void *>(&gemm_bf16_mfma_kernel<BM, BN, WM, WN, EPI>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_bf16_mfma_kernel<BM, BN, WM, WN>), dim3(grid_tiles(a, BM, BN)),
+  hipLaunchKernelGGL((gemm_bf16_mfma_kernel<BM, BN, WM, WN, EPI>), dim3(grid_tiles(a, BM, BN)),
                      dim3(WM * WN * 64), kSmem, s, a);
   return hipGetLastError();
+}
+
+template <int EPI>
+hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
+  const int64_t rows_per_group = a.M / (a.n_groups > 0 ? a.n_groups : 1);
+  if (rows_per_group >= 1024 && a.N >= 256) return launch_mfma<256, 256, 2, 2, EPI>(a, s);
+  if (rows_per_group >= 96) return launch_mfma<128, 128, 2, 2, EPI>(a, s);
+  return launch_mfma<64, 128, 2, 2, EPI>(a, s);
 }
 
 }  // namespace
 
 hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
-  const bool mfma_ok = a.dtype == ROM_DTYPE_BF16 && a.K % 8 == 0 && a.lda % 8 == 0 &&
-                       (reinterpret_cast<uintptr_t>(a.A) % 16 == 0) &&
-                       (reinterpret_cast<uintptr_t>(a.W) % 16 == 0);
+  const bool mfma_ok = a.dtype == ROM_DTYPE_BF16 && a.K % 8 == 0 && a.lda % 8 == 0 && a.N % 4 == 0 &&
+                       a.ldc % 4 == 0 && (reinterpret_cast<uintptr_t>(a.A) % 16 == 0) &&
+                       (reinterpret_cast<uintptr_t>(a.W) % 16 == 0) &&
+                       (reinterpret_cast<uintptr_t>(a.C) % 16 == 0) &&
+                       !(a.bias && !a.softplus) && !(a.softplus && !a.bias) &&
+                       !(a.row_scale && (a.bias || a.c_is_f32)) && !(a.bias && a.c_is_f32);
   if (!mfma_ok) {
     const dim3 grid(grid_tiles(a, kSB, kSB));
     if (a.dtype == ROM_DTYPE_BF16)
@@ -302,20 +391,22 @@ hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s) {
       hipLaunchKernelGGL(gemm_simple_kernel<float>, grid, dim3(256), 0, s, a);
     return hipGetLastError();
   }
-  const int64_t rows_per_group = a.M / (a.n_groups > 0 ? a.n_groups : 1);
-  if (a.N <= 192) {
-    switch ((a.N + 31) / 32) {
-      case 1: return launch_mfma<128, 32, 4, 1>(a, s);
-      case 2: return launch_mfma<128, 64, 4, 1>(a, s);
-      case 3: return launch_mfma<128, 96, 4, 1>(a, s);
-      case 4: return launch_mfma<128, 128, 4, 1>(a, s);
-      case 5: return launch_mfma<128, 160, 4, 1>(a, s);
-      default: return launch_mfma<128, 192, 4, 1>(a, s);
+  if (a.c_is_f32) {
+    if (a.N <= 192) {
+      switch ((a.N + 31) / 32) {
+        case 1: return launch_mfma<128, 32, 4, 1, kEpiPlainF32>(a, s);
+        case 2: return launch_mfma<128, 64, 4, 1, kEpiPlainF32>(a, s);
+        case 3: return launch_mfma<128, 96, 4, 1, kEpiPlainF32>(a, s);
+        case 4: return launch_mfma<128, 128, 4, 1, kEpiPlainF32>(a, s);
+        case 5: return launch_mfma<128, 160, 4, 1, kEpiPlainF32>(a, s);
+        default: return launch_mfma<128, 192, 4, 1, kEpiPlainF32>(a, s);
+      }
     }
+    return launch_mfma_tiles<kEpiPlainF32>(a, s);
   }
-  if (rows_per_group >= 1024) return launch_mfma<256, 256, 2, 2>(a, s);
-  if (rows_per_group >= 96) return launch_mfma<128, 128, 2, 2>(a, s);
-  return launch_mfma<64, 128, 2, 2>(a, s);
+  if (a.bias) return launch_mfma_tiles<kEpiBiasSoftplus>(a, s);
+  if (a.row_scale) return launch_mfma_tiles<kEpiRowScale>(a, s);
+  return launch_mfma_tiles<kEpiPlain>(a, s);
 }
 
 }  // namespace rom
