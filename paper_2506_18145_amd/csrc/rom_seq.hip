@@ -154,13 +154,22 @@ __global__ __launch_bounds__(256) void conv_silu_kernel(
 
 // ------------------------------------------------------------------ selective scan, Eq. (5)
 // Lane = (channel, state): 16 lanes share a channel, a 256-thread block owns 16 channels of one
-// sequence and walks the whole sequence once, the 16 states of every channel living in registers
-// (one per lane).  Inputs come through LDS in tiles of kScanTile steps; inside a tile, 16 steps at
-// a time: lane n of a channel fetches dt and u of step n, the per-step values are handed round
-// with row broadcasts, and the 16 products C_n*h_n of 16 steps are summed with a transposing
-// butterfly so that lane n ends up with y of step n and does that step's D skip and SiLU(z) gate.
+// sequence and walks the whole sequence once; the 16 states of a channel live in registers, one
+// per lane, so the recurrence needs no second pass and no carry fix-up.
+// Work is cut into tiles of kScanTile steps and groups of 16 steps:
+//   * the block fetches a tile of dt, u, z (16 channels wide) and of B_t, C_t with 8/16-byte
+//     loads one tile ahead of use (registers), then parks it in double-buffered LDS as floats;
+//     B/C are stored transposed so that lane n reads B_{t,n}, C_{t,n} of four steps at once;
+//   * lane n of a channel picks up dt, u, z of step n of a group and hands dt and dt*u round
+//     with DPP row broadcasts;
+//   * the 16 products C_n*h_n of 16 steps are summed by a transposing butterfly (15 DPP adds per
+//     step pair instead of a full reduction per step) that leaves y of step n in lane n, which
+//     then applies the D skip and the SiLU(z) gate; g leaves through LDS in 4-channel packets.
 constexpr int kScanTile = 64;
+constexpr int kScanGroups = kScanTile / 16;
 constexpr int kScanCh = 16;
+constexpr int kBcPitch = kScanTile + 4;     // floats; keeps 16-byte alignment of the row reads
+constexpr int kChPitch = kScanCh + 4;       // floats per step row of the dt/u/z/g tiles
 
 template <int CTRL> __device__ __forceinline__ float dpp(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
@@ -171,55 +180,139 @@ constexpr int kDppHalfMirror = 0x141;   // lane i <-> 7 - i inside each 8
 constexpr int kDppRowMirror = 0x140;    // lane i <-> 15 - i inside each 16
 constexpr int kDppRowBcast0 = 0x150;    // row_newbcast:0 (+j for lane j of the row)
 
-struct ScanSmem {
-  float dt[kScanTile][kScanCh];
-  float u[kScanTile][kScanCh];
-  float z[kScanTile][kScanCh];
-  float bc[32][kScanTile + 4];          // transposed: [B_0..B_15, C_0..C_15][step]
-  float g[kScanTile][kScanCh];
+struct __attribute__((aligned(16))) ScanSmem {
+  float dt[2][kScanTile][kChPitch];
+  float u[2][kScanTile][kChPitch];
+  float z[2][kScanTile][kChPitch];
+  float bc[2][32][kBcPitch];            // [buffer][B_0..B_15, C_0..C_15][step]
+  float g[2][kScanTile][kChPitch];
 };
 
 template <int J> struct StepSeq {
   __device__ static __forceinline__ void run(float dt_r, float dtu_r, float a2, const float *bv,
-                                             const float *cv, float &h, float *p) {
-    StepSeq<J - 1>::run(dt_r, dtu_r, a2, bv, cv, h, p);
+                                             float &h, float *hs) {
+    StepSeq<J - 1>::run(dt_r, dtu_r, a2, bv, h, hs);
     const float dtj = dpp<kDppRowBcast0 + J>(dt_r);
     const float dtuj = dpp<kDppRowBcast0 + J>(dtu_r);
     const float da = fast_exp2(dtj * a2);
     h = fmaf(da, h, dtuj * bv[J]);
-    p[J] = h * cv[J];
+    hs[J] = h;
   }
 };
 template <> struct StepSeq<-1> {
-  __device__ static __forceinline__ void run(float, float, float, const float *, const float *,
-                                             float &, float *) {}
+  __device__ static __forceinline__ void run(float, float, float, const float *, float &, float *) {}
 };
 
-// Sum p[j] over the 16 lanes of a row for every j; lane i returns the total of p[i].
-__device__ __forceinline__ float transpose_reduce16(const float *p, int n) {
+// p[j] = hs[j] * cv[j]; sum p[j] over the 16 lanes of a row for every j; lane i returns the
+// total of p[i].  Contraction is off so that every "x + dpp(x)" stays one DPP add.
+__device__ __forceinline__ float transpose_reduce16(const float *hs, const float *cv, int n) {
+#pragma clang fp contract(off)
   float a[8], b[4], c[2];
   const bool hi8 = (n & 8) != 0, hi4 = (n & 4) != 0, hi2 = (n & 2) != 0, hi1 = (n & 1) != 0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const float lo = p[j] + dpp<kDppRowMirror>(p[j]);
-    const float hi = p[j + 8] + dpp<kDppRowMirror>(p[j + 8]);
+    const float pl = hs[j] * cv[j], ph = hs[j + 8] * cv[j + 8];
+    const float lo = dpp<kDppRowMirror>(pl) + pl;
+    const float hi = dpp<kDppRowMirror>(ph) + ph;
     a[j] = hi8 ? hi : lo;
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const float lo = a[j] + dpp<kDppHalfMirror>(a[j]);
-    const float hi = a[j + 4] + dpp<kDppHalfMirror>(a[j + 4]);
+    const float lo = dpp<kDppHalfMirror>(a[j]) + a[j];
+    const float hi = dpp<kDppHalfMirror>(a[j + 4]) + a[j + 4];
     b[j] = hi4 ? hi : lo;
   }
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    const float lo = b[j] + dpp<kDppQuadRev>(b[j]);
-    const float hi = b[j + 2] + dpp<kDppQuadRev>(b[j + 2]);
+    const float lo = dpp<kDppQuadRev>(b[j]) + b[j];
+    const float hi = dpp<kDppQuadRev>(b[j + 2]) + b[j + 2];
     c[j] = hi2 ? hi : lo;
   }
-  const float lo = c[0] + dpp<kDppQuadXor1>(c[0]);
-  const float hi = c[1] + dpp<kDppQuadXor1>(c[1]);
+  const float lo = dpp<kDppQuadXor1>(c[0]) + c[0];
+  const float hi = dpp<kDppQuadXor1>(c[1]) + c[1];
   return hi1 ? hi : lo;
+}
+
+// N consecutive elements of T held in registers
+template <typename T, int N> struct Pack;
+template <> struct Pack<bf16_t, 8> {
+  uint4 raw;
+  __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const uint4 *>(p); }
+  __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
+  __device__ __forceinline__ float get(int i) const {
+    const unsigned int w = (&raw.x)[i >> 1];
+    return __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16));
+  }
+};
+template <> struct Pack<bf16_t, 4> {
+  uint2 raw;
+  __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const uint2 *>(p); }
+  __device__ __forceinline__ void zero() { raw = make_uint2(0, 0); }
+  __device__ __forceinline__ float get(int i) const {
+    const unsigned int w = (&raw.x)[i >> 1];
+    return __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16));
+  }
+};
+template <> struct Pack<float, 8> {
+  float4 lo, hi;
+  __device__ __forceinline__ void load(const float *p) {
+    lo = *reinterpret_cast<const float4 *>(p);
+    hi = *reinterpret_cast<const float4 *>(p + 4);
+  }
+  __device__ __forceinline__ void zero() { lo = make_float4(0.f, 0.f, 0.f, 0.f); hi = lo; }
+  __device__ __forceinline__ float get(int i) const { return i < 4 ? (&lo.x)[i] : (&hi.x)[i - 4]; }
+};
+template <> struct Pack<float, 4> {
+  float4 raw;
+  __device__ __forceinline__ void load(const float *p) { raw = *reinterpret_cast<const float4 *>(p); }
+  __device__ __forceinline__ void zero() { raw = make_float4(0.f, 0.f, 0.f, 0.f); }
+  __device__ __forceinline__ float get(int i) const { return (&raw.x)[i]; }
+};
+
+// One thread's share of a tile: 8 channels of one step of dt (threads 0..127) or u (128..255),
+// 4 channels of one step of z, 8 of the 32 B/C values of one step.
+template <typename T> struct ScanStage {
+  Pack<T, 8> du;
+  Pack<T, 4> z;
+  float4 bc0, bc1;
+};
+
+template <typename T, bool kTail>
+__device__ __forceinline__ void scan_fetch(ScanStage<T> &r, const T *dt_b, const T *u_b, const T *z_b,
+                                           const float *bc_b, int64_t t0, int64_t L, int d_inner,
+                                           int64_t ld_z, int tid) {
+  const int64_t t_du = t0 + ((tid & 127) >> 1);
+  if (!kTail || t_du < L) r.du.load((tid < 128 ? dt_b : u_b) + t_du * d_inner + (tid & 1) * 8);
+  else r.du.zero();
+  const int64_t t_z = t0 + (tid >> 2);
+  if (!kTail || t_z < L) {
+    r.z.load(z_b + t_z * ld_z + (tid & 3) * 4);
+    const float4 *src = reinterpret_cast<const float4 *>(bc_b + t_z * 32 + (tid & 3) * 8);
+    r.bc0 = src[0];
+    r.bc1 = src[1];
+  } else {
+    r.z.zero();
+    r.bc0 = make_float4(0.f, 0.f, 0.f, 0.f);
+    r.bc1 = r.bc0;
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ void scan_park(ScanSmem &sm, int buf, const ScanStage<T> &r, int tid) {
+  {
+    float *dst = (tid < 128 ? &sm.dt[buf][0][0] : &sm.u[buf][0][0]) + ((tid & 127) >> 1) * kChPitch +
+                 (tid & 1) * 8;
+    *reinterpret_cast<float4 *>(dst) = make_float4(r.du.get(0), r.du.get(1), r.du.get(2), r.du.get(3));
+    *reinterpret_cast<float4 *>(dst + 4) = make_float4(r.du.get(4), r.du.get(5), r.du.get(6), r.du.get(7));
+  }
+  const int row = tid >> 2, part = tid & 3;
+  *reinterpret_cast<float4 *>(&sm.z[buf][row][part * 4]) =
+      make_float4(r.z.get(0), r.z.get(1), r.z.get(2), r.z.get(3));
+  const int col = part * 8;
+  sm.bc[buf][col + 0][row] = r.bc0.x; sm.bc[buf][col + 1][row] = r.bc0.y;
+  sm.bc[buf][col + 2][row] = r.bc0.z; sm.bc[buf][col + 3][row] = r.bc0.w;
+  sm.bc[buf][col + 4][row] = r.bc1.x; sm.bc[buf][col + 5][row] = r.bc1.y;
+  sm.bc[buf][col + 6][row] = r.bc1.z; sm.bc[buf][col + 7][row] = r.bc1.w;
 }
 
 template <typename T>
@@ -230,7 +323,7 @@ __global__ __launch_bounds__(256) void scan_gate_kernel(
     T *__restrict__ g, int64_t L, int d_inner) {
   __shared__ ScanSmem sm;
   const int tid = threadIdx.x;
-  const int n = tid & 15;            // state index
+  const int n = tid & 15;            // state index = lane inside the DPP row
   const int cl = tid >> 4;           // channel inside the block
   // consecutive workgroups land on different XCDs (round-robin over 8): give each XCD a
   // contiguous run of channel groups so that neighbours in memory share an L2.
@@ -251,51 +344,57 @@ __global__ __launch_bounds__(256) void scan_gate_kernel(
   const float *bc_b = bc + b * L * 32;
   T *g_b = g + b * L * d_inner + c0;
 
-  // staging roles: thread -> (row, 4-channel quarter) of the dt/u/z tiles, (row, 8-float part) of bc
-  const int s_row = tid >> 2, s_q = (tid & 3) * 4;
+  ScanStage<T> st;
+  const int64_t n_tiles = (L + kScanTile - 1) / kScanTile;
+  if (L >= kScanTile) scan_fetch<T, false>(st, dt_b, u_b, z_b, bc_b, 0, L, d_inner, ld_z, tid);
+  else scan_fetch<T, true>(st, dt_b, u_b, z_b, bc_b, 0, L, d_inner, ld_z, tid);
+  scan_park<T>(sm, 0, st, tid);
+  __syncthreads();
 
-  for (int64_t t0 = 0; t0 < L; t0 += kScanTile) {
-    __syncthreads();                 // previous tile fully consumed
-    {
-      const int64_t t = t0 + s_row;
-      const bool ok = t < L;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        sm.dt[s_row][s_q + i] = ok ? to_f32(dt_b[t * d_inner + s_q + i]) : 0.0f;
-        sm.u[s_row][s_q + i] = ok ? to_f32(u_b[t * d_inner + s_q + i]) : 0.0f;
-        sm.z[s_row][s_q + i] = ok ? to_f32(z_b[t * ld_z + s_q + i]) : 0.0f;
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int col = (tid & 3) * 8 + i;
-        sm.bc[col][s_row] = ok ? bc_b[t * 32 + col] : 0.0f;
-      }
+  for (int64_t ti = 0; ti < n_tiles; ++ti) {
+    const int buf = static_cast<int>(ti & 1);
+    const int64_t t0 = ti * kScanTile;
+    const bool has_next = ti + 1 < n_tiles;
+    if (has_next) {     // next tile's inputs travel while this tile is computed
+      if (t0 + 2 * kScanTile <= L)
+        scan_fetch<T, false>(st, dt_b, u_b, z_b, bc_b, t0 + kScanTile, L, d_inner, ld_z, tid);
+      else
+        scan_fetch<T, true>(st, dt_b, u_b, z_b, bc_b, t0 + kScanTile, L, d_inner, ld_z, tid);
     }
-    __syncthreads();
-
-#pragma unroll 1
-    for (int s0 = 0; s0 < kScanTile; s0 += 16) {
-      const float dt_r = sm.dt[s0 + n][cl];
-      const float u_r = sm.u[s0 + n][cl];
+#pragma unroll
+    for (int gi = 0; gi < kScanGroups; ++gi) {
+      const int s0 = gi * 16;
+      const float dt_r = sm.dt[buf][s0 + n][cl];
+      const float u_r = sm.u[buf][s0 + n][cl];
+      const float z_r = sm.z[buf][s0 + n][cl];
       const float dtu_r = dt_r * u_r;
-      float bv[16], cv[16], p[16];
+      float bv[16], cv[16], hs[16];
 #pragma unroll
       for (int j = 0; j < 16; j += 4) {
-        const float4 b4 = *reinterpret_cast<const float4 *>(&sm.bc[n][s0 + j]);
-        const float4 c4 = *reinterpret_cast<const float4 *>(&sm.bc[16 + n][s0 + j]);
+        const float4 b4 = *reinterpret_cast<const float4 *>(&sm.bc[buf][n][s0 + j]);
+        const float4 c4 = *reinterpret_cast<const float4 *>(&sm.bc[buf][16 + n][s0 + j]);
         bv[j] = b4.x; bv[j + 1] = b4.y; bv[j + 2] = b4.z; bv[j + 3] = b4.w;
         cv[j] = c4.x; cv[j + 1] = c4.y; cv[j + 2] = c4.z; cv[j + 3] = c4.w;
       }
-      StepSeq<15>::run(dt_r, dtu_r, a2, bv, cv, h, p);
-      const float y = transpose_reduce16(p, n) + d_skip * u_r;
-      sm.g[s0 + n][cl] = y * silu_f32(sm.z[s0 + n][cl]);
+      StepSeq<15>::run(dt_r, dtu_r, a2, bv, h, hs);
+      const float y = transpose_reduce16(hs, cv, n) + d_skip * u_r;
+      sm.g[buf][s0 + n][cl] = y * silu_f32(z_r);
     }
+    if (has_next) scan_park<T>(sm, buf ^ 1, st, tid);
     __syncthreads();
-    {
-      const int64_t t = t0 + s_row;
+    {   // g of this tile: thread -> (step row, 4 channels)
+      const int r = tid >> 2, q = (tid & 3) * 4;
+      const int64_t t = t0 + r;
       if (t < L) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) g_b[t * d_inner + s_q + i] = from_f32<T>(sm.g[s_row][s_q + i]);
+        const float4 v = *reinterpret_cast<const float4 *>(&sm.g[buf][r][q]);
+        if (sizeof(T) == 2) {
+          uint2 pk;
+          pk.x = static_cast<unsigned int>(f32_to_bf16(v.x)) | (static_cast<unsigned int>(f32_to_bf16(v.y)) << 16);
+          pk.y = static_cast<unsigned int>(f32_to_bf16(v.z)) | (static_cast<unsigned int>(f32_to_bf16(v.w)) << 16);
+          *reinterpret_cast<uint2 *>(g_b + t * d_inner + q) = pk;
+        } else {
+          *reinterpret_cast<float4 *>(g_b + t * d_inner + q) = v;
+        }
       }
     }
   }
