@@ -162,7 +162,7 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   GemmArgs ga;
   memset(&ga, 0, sizeof(ga));
   ga.dtype = d->dtype;
-  ga.A = x; ga.lda = Dm; ga.a_rows = tok_of_pos;
+  ga.A = x; ga.lda = Dm; ga.a_rows = tok_of_pos; ga.a_span = N * Dm;
   ga.W = w->w_in; ga.offsets = offsets; ga.n_groups = E;
   ga.M = S; ga.N = 2 * De; ga.K = Dm;
   ga.C = multi ? at(p.xz_sorted) : at(p.xz); ga.ldc = 2 * De; ga.c_rows = multi ? nullptr : tok_of_pos;
@@ -187,7 +187,7 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   // x projection -> dt_low | B | C
   memset(&ga, 0, sizeof(ga));
   ga.dtype = d->dtype;
-  ga.A = at(p.u); ga.lda = De;
+  ga.A = at(p.u); ga.lda = De; ga.a_span = N * De;
   ga.W = w->w_x; ga.N = R + 32; ga.K = De;
   ga.C = at(p.xdbl); ga.ldc = R + 32; ga.c_is_f32 = 1;
   if (routed_xdt) {
@@ -205,7 +205,7 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   // dt projection + bias + softplus
   memset(&ga, 0, sizeof(ga));
   ga.dtype = d->dtype;
-  ga.A = at(p.dt_low); ga.lda = R;
+  ga.A = at(p.dt_low); ga.lda = R; ga.a_span = N * R;
   ga.W = w->w_dt; ga.N = De; ga.K = R;
   if (routed_xdt && multi) {
     ga.a_rows = tok_of_pos; ga.offsets = offsets; ga.n_groups = E; ga.M = S;
@@ -232,7 +232,7 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   // out projection, Eq. (13), and the gate-weighted combine, Eq. (12)
   memset(&ga, 0, sizeof(ga));
   ga.dtype = d->dtype;
-  ga.A = at(p.g); ga.lda = De; ga.a_rows = tok_of_pos;
+  ga.A = at(p.g); ga.lda = De; ga.a_rows = tok_of_pos; ga.a_span = N * De;
   ga.W = w->w_out; ga.offsets = offsets; ga.n_groups = E;
   ga.M = S; ga.N = Dm; ga.K = De;
   if (multi) {

@@ -9,6 +9,8 @@
 // Group sizes live in device memory: every workgroup finds its (expert, row tile) by walking
 // the offsets, so skewed loads only change how many tiles an expert contributes.
 // fp32 path (and shapes the MFMA kernel does not take): a plain LDS-tiled FMA kernel.
+#include <type_traits>
+
 #include "rom_internal.h"
 
 namespace rom {
@@ -94,8 +96,16 @@ __device__ __forceinline__ void store_out(const GemmArgs &a, int64_t crow, int c
 // ------------------------------------------------------------------ bf16 MFMA kernel
 constexpr int kBK = 64;                 // K slab, 8 chunks of 8 bf16 (16 bytes) per row
 constexpr int kRowChunks = kBK / 8;
+// LDS swizzle: chunk c of tile row r lives in slot c ^ lds_swizzle(r) of that row.  Two rows span
+// the 64 four-byte banks, and a 16-byte-per-lane read is served 16 lanes (rows) at a time, so 16
+// consecutive rows reading the same logical chunk must land in 16 different (row parity, slot)
+// pairs; (r & 7) ^ ((r >> 3) & 1) does that and stays conflict-free on 8-row groups as well.
+__device__ __forceinline__ int lds_swizzle(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+// PA / PB: how many K slabs ahead the global loads of the activation / weight operand run
+// (1 or 2; each extra slab costs one more register set for that operand).
+// KTAIL: K is not a multiple of the slab, the last slab is zero-filled past K.
+template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL, int PA = 2, int PB = 2>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmArgs a) {
   constexpr int NT = WM * WN * 64;
   constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
@@ -119,59 +129,77 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
   // global source of every 16-byte chunk this thread stages.  Rows past the end of the tile are
   // redirected to its first row (their results are never stored), so the loads need no branch;
   // a K tail is zero-filled by a select.
-  int64_t a_src[A_CH], b_src[B_CH];
+  // (32-bit element offsets from the operand bases: the launcher checks that both operands span
+  // less than 2^32 elements, and registers are scarce here)
+  uint32_t a_src[A_CH], b_src[B_CH];
 #pragma unroll
   for (int i = 0; i < A_CH; ++i) {
     const int q = tid + i * NT, r = q / kRowChunks;
     int64_t p = tc.row0 + r;
     if (p >= tc.row_end) p = tc.row0;
-    a_src[i] = static_cast<int64_t>(a.a_rows ? a.a_rows[p] : p) * a.lda;
+    a_src[i] = static_cast<uint32_t>((a.a_rows ? a.a_rows[p] : p) * a.lda);
   }
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) {
     const int q = tid + i * NT, r = q / kRowChunks;
     const int n = (tc.n0 + r < a.N) ? tc.n0 + r : a.N - 1;
-    b_src[i] = static_cast<int64_t>(n) * a.K;
+    b_src[i] = static_cast<uint32_t>(n) * static_cast<uint32_t>(a.K);
   }
   const int k_chunk = (tid % kRowChunks) * 8;
   const int k_last = a.K - 8;
 
-  uint4 ra[A_CH], rb[B_CH];
-  // full slab: every chunk lies inside K, plain unconditional loads
-  auto load_full = [&](int k0) {
+  // Register sets for slabs in flight: with depth 2 the global loads of slab kt+2 are issued while
+  // slab kt is multiplied, so they have two slab times to land before they are parked in LDS
+  // (HBM latency is longer than one slab of MFMA work).
+  // (separate arrays with compile-time selection: the compiler keeps them in registers only if
+  // every index is a constant and the arrays are never passed around by reference)
+  uint4 ra0[A_CH], ra1[A_CH], rb0[B_CH], rb1[B_CH];
+  auto load_a = [&](int k0, auto set) __attribute__((always_inline)) {
+    constexpr int S = decltype(set)::value;
     const int k = k0 + k_chunk;
+    const bool k_ok = !KTAIL || k <= k_last;
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) ra[i] = *reinterpret_cast<const uint4 *>(Ap + a_src[i] + k);
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const uint4 *>(Wp + b_src[i] + k);
+    for (int i = 0; i < A_CH; ++i) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (!KTAIL || k0 + kBK <= a.K) v = *reinterpret_cast<const uint4 *>(Ap + a_src[i] + k);
+      else if (k_ok) v = *reinterpret_cast<const uint4 *>(Ap + a_src[i] + k);
+      if constexpr (S == 0) ra0[i] = v; else ra1[i] = v;
+    }
   };
-  // last slab when K is not a multiple of the slab: chunks past K are zero
-  auto load_tail = [&](int k0) {
+  auto load_b = [&](int k0, auto set) __attribute__((always_inline)) {
+    constexpr int S = decltype(set)::value;
     const int k = k0 + k_chunk;
-    const bool k_ok = k <= k_last;
+    const bool k_ok = !KTAIL || k <= k_last;
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i)
-      ra[i] = k_ok ? *reinterpret_cast<const uint4 *>(Ap + a_src[i] + k) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i)
-      rb[i] = k_ok ? *reinterpret_cast<const uint4 *>(Wp + b_src[i] + k) : make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < B_CH; ++i) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (!KTAIL || k0 + kBK <= a.K) v = *reinterpret_cast<const uint4 *>(Wp + b_src[i] + k);
+      else if (k_ok) v = *reinterpret_cast<const uint4 *>(Wp + b_src[i] + k);
+      if constexpr (S == 0) rb0[i] = v; else rb1[i] = v;
+    }
   };
-  auto load_global = [&](int k0) {
-    if (k0 + kBK <= a.K) load_full(k0);
-    else load_tail(k0);
-  };
-  auto store_lds = [&](int buf) {
+  auto park_a = [&](int buf, auto set) __attribute__((always_inline)) {
+    constexpr int S = decltype(set)::value;
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
       const int q = tid + i * NT, r = q / kRowChunks, c = q % kRowChunks;
-      As[buf * BM * kRowChunks + r * kRowChunks + (c ^ (r & 7))] = ra[i];
+      uint4 v;
+      if constexpr (S == 0) v = ra0[i]; else v = ra1[i];
+      As[buf * BM * kRowChunks + r * kRowChunks + (c ^ lds_swizzle(r))] = v;
     }
+  };
+  auto park_b = [&](int buf, auto set) __attribute__((always_inline)) {
+    constexpr int S = decltype(set)::value;
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) {
       const int q = tid + i * NT, r = q / kRowChunks, c = q % kRowChunks;
-      Bs[buf * BN * kRowChunks + r * kRowChunks + (c ^ (r & 7))] = rb[i];
+      uint4 v;
+      if constexpr (S == 0) v = rb0[i]; else v = rb1[i];
+      Bs[buf * BN * kRowChunks + r * kRowChunks + (c ^ lds_swizzle(r))] = v;
     }
   };
+  using Set0 = std::integral_constant<int, 0>;
+  using Set1 = std::integral_constant<int, 1>;
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -183,13 +211,13 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
 
   const int KT = (a.K + kBK - 1) / kBK;
   const int frag_row = lane & 31, frag_half = lane >> 5;
-  // LDS chunk index of this lane's fragment for 16-wide K step kk: row * 8 + ((2 kk + half) ^ (row & 7));
-  // the wave / tile row offsets are multiples of 8, so the swizzle term depends on the lane only.
+  // LDS chunk index of this lane's fragment for 16-wide K step kk: row * 8 + ((2 kk + half) ^ swizzle(row));
+  // the wave / tile row offsets are multiples of 32, so the swizzle term depends on the lane only.
   const int a_base = (wm * WTM + frag_row) * kRowChunks, b_base = (wn * WTN + frag_row) * kRowChunks;
-  const int swz = frag_row & 7;
+  const int swz = lds_swizzle(frag_row);
 
   bf16x8_t fa[2][TM], fb[2][TN];
-  auto load_frags = [&](int buf, int kk, bf16x8_t(&af)[TM], bf16x8_t(&bfr)[TN]) {
+  auto load_frags = [&](int buf, int kk, bf16x8_t(&af)[TM], bf16x8_t(&bfr)[TN]) __attribute__((always_inline)) {
     const int c = (kk * 2 + frag_half) ^ swz;
     const uint4 *Ab = As + buf * BM * kRowChunks + a_base + c;
     const uint4 *Bb = Bs + buf * BN * kRowChunks + b_base + c;
@@ -204,7 +232,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
       bfr[j] = *reinterpret_cast<const bf16x8_t *>(&v);
     }
   };
-  auto mma = [&](const bf16x8_t(&af)[TM], const bf16x8_t(&bfr)[TN]) {
+  auto mma = [&](const bf16x8_t(&af)[TM], const bf16x8_t(&bfr)[TN]) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -212,7 +240,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
   };
   // ask the scheduler to spread the next step's LDS fragment reads between this step's MFMAs
-  auto interleave_reads = [&]() {
+  auto interleave_reads = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < TM + TN; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                       // one DS read
@@ -220,31 +248,51 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
     }
   };
 
-  load_global(0);
-  store_lds(0);
+  load_a(0, Set0{});
+  load_b(0, Set0{});
+  park_a(0, Set0{});
+  park_b(0, Set0{});
+  const int k_end = (KT - 1) * kBK;      // loads past the last slab are redirected to it (and never used)
+  if (PA == 2) load_a(kBK < k_end ? kBK : k_end, Set1{});
+  if (PB == 2) load_b(kBK < k_end ? kBK : k_end, Set1{});
   __syncthreads();
   load_frags(0, 0, fa[0], fb[0]);
 
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    const bool has_next = kt + 1 < KT;
-    if (has_next) load_global((kt + 1) * kBK);        // lands while this slab is multiplied
-    load_frags(cur, 1, fa[1], fb[1]);
+  // One K slab, free of conditionals: PAR = kt & 1 selects the LDS buffer being read; slab s of an
+  // operand with depth P travels in register set s % P.  The slab after the last one is "loaded"
+  // and parked like any other (clamped address, buffer nobody reads again).
+  auto slab = [&](int kt, auto par) __attribute__((always_inline)) {
+    constexpr int PAR = decltype(par)::value;
+    using LoadA = std::integral_constant<int, PA == 2 ? PAR : 0>;
+    using LoadB = std::integral_constant<int, PB == 2 ? PAR : 0>;
+    using ParkA = std::integral_constant<int, PA == 2 ? (PAR ^ 1) : 0>;
+    using ParkB = std::integral_constant<int, PB == 2 ? (PAR ^ 1) : 0>;
+    const int ka = (kt + PA) * kBK, kb = (kt + PB) * kBK;
+    load_a(ka < k_end ? ka : k_end, LoadA{});
+    load_b(kb < k_end ? kb : k_end, LoadB{});
+    load_frags(PAR, 1, fa[1], fb[1]);
     mma(fa[0], fb[0]);
     interleave_reads();
-    load_frags(cur, 2, fa[0], fb[0]);
+    load_frags(PAR, 2, fa[0], fb[0]);
     mma(fa[1], fb[1]);
     interleave_reads();
-    load_frags(cur, 3, fa[1], fb[1]);
+    load_frags(PAR, 3, fa[1], fb[1]);
     mma(fa[0], fb[0]);
     interleave_reads();
-    // every fragment of this slab is in registers: stage the next slab, then overlap the
-    // fetch of its first fragments with the last 16-wide step of this one
-    if (has_next) store_lds(cur ^ 1);
+    // every fragment of this slab is in registers: park the next slab, then overlap the fetch
+    // of its first fragments with the last 16-wide step of this one
+    park_a(PAR ^ 1, ParkA{});
+    park_b(PAR ^ 1, ParkB{});
     __syncthreads();
-    if (has_next) load_frags(cur ^ 1, 0, fa[0], fb[0]);
+    load_frags(PAR ^ 1, 0, fa[0], fb[0]);
     mma(fa[1], fb[1]);
+  };
+  int kt = 0;
+  for (; kt + 1 < KT; kt += 2) {
+    slab(kt, Set0{});
+    slab(kt + 1, Set1{});
   }
+  if (kt < KT) slab(kt, Set0{});
 
   // epilogue.  The weight fragment is the MFMA's row operand, so a lane holds, for ONE output row
   // (tile row lane%32), the output columns 8*q + 4*(lane/32) + r of each 32-wide tile in
@@ -349,20 +397,25 @@ int grid_tiles(const GemmArgs &a, int BM, int BN) {
   return static_cast<int>(g);
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
-hipError_t launch_mfma(const GemmArgs &a, hipStream_t s) {
+template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL>
+hipError_t launch_mfma_k(const GemmArgs &a, hipStream_t s) {
   constexpr int kSmem = 2 * (BM + BN) * kRowChunks * 16;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(
-        reinterpret_cast<const void *>(&gemm_bf16_mfma_kernel<BM, BN, WM, WN, EPI>),
+        reinterpret_cast<const void *>(&gemm_bf16_mfma_kernel<BM, BN, WM, WN, EPI, KTAIL>),
         hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_bf16_mfma_kernel<BM, BN, WM, WN, EPI>), dim3(grid_tiles(a, BM, BN)),
+  hipLaunchKernelGGL((gemm_bf16_mfma_kernel<BM, BN, WM, WN, EPI, KTAIL>), dim3(grid_tiles(a, BM, BN)),
                      dim3(WM * WN * 64), kSmem, s, a);
   return hipGetLastError();
+}
+template <int BM, int BN, int WM, int WN, int EPI>
+hipError_t launch_mfma(const GemmArgs &a, hipStream_t s) {
+  if (a.K % kBK == 0) return launch_mfma_k<BM, BN, WM, WN, EPI, false>(a, s);
+  return launch_mfma_k<BM, BN, WM, WN, EPI, true>(a, s);
 }
 
 template <int EPI>
@@ -380,7 +433,8 @@ hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s) {
   const bool mfma_ok = a.dtype == ROM_DTYPE_BF16 && a.K % 8 == 0 && a.lda % 8 == 0 && a.N % 4 == 0 &&
                        a.ldc % 4 == 0 && (reinterpret_cast<uintptr_t>(a.A) % 16 == 0) &&
                        (reinterpret_cast<uintptr_t>(a.W) % 16 == 0) &&
-                       (reinterpret_cast<uintptr_t>(a.C) % 16 == 0) &&
+                       (reinterpret_cast<uintptr_t>(a.C) % 16 == 0) && a.a_span < (1ll << 32) &&
+                       static_cast<int64_t>(a.N) * a.K < (1ll << 32) &&
                        !(a.bias && !a.softplus) && !(a.softplus && !a.bias) &&
                        !(a.row_scale && (a.bias || a.c_is_f32)) && !(a.bias && a.c_is_f32);
   if (!mfma_ok) {

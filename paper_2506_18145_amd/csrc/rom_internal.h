@@ -52,6 +52,7 @@ struct GemmArgs {
   const void *A;             // [*, lda]
   int64_t lda;
   const int32_t *a_rows;     // row of A for position p, NULL = p
+  int64_t a_span;            // number of elements of A that may be addressed (rows * lda)
   const void *W;             // [n_groups, N, K] row-major
   const int32_t *offsets;    // NULL = single group
   int n_groups;
