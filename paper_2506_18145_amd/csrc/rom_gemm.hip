@@ -221,15 +221,20 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
     const int c = (kk * 2 + frag_half) ^ swz;
     const uint4 *Ab = As + buf * BM * kRowChunks + a_base + c;
     const uint4 *Bb = Bs + buf * BN * kRowChunks + b_base + c;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const uint4 v = Ab[i * 32 * kRowChunks];
-      af[i] = *reinterpret_cast<const bf16x8_t *>(&v);
+    // issue order = order of first use by mma(): A row 0, then every B column, then the other A rows
+    {
+      const uint4 v = Ab[0];
+      af[0] = *reinterpret_cast<const bf16x8_t *>(&v);
     }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const uint4 v = Bb[j * 32 * kRowChunks];
       bfr[j] = *reinterpret_cast<const bf16x8_t *>(&v);
+    }
+#pragma unroll
+    for (int i = 1; i < TM; ++i) {
+      const uint4 v = Ab[i * 32 * kRowChunks];
+      af[i] = *reinterpret_cast<const bf16x8_t *>(&v);
     }
   };
   auto mma = [&](const bf16x8_t(&af)[TM], const bf16x8_t(&bfr)[TN]) __attribute__((always_inline)) {
@@ -239,13 +244,15 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
       for (int j = 0; j < TN; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
   };
-  // ask the scheduler to spread the next step's LDS fragment reads between this step's MFMAs
+  // ask the scheduler to put the next step's LDS fragment reads between the first MFMAs of this
+  // step (one read per MFMA), so that every fragment has most of a step to arrive
   auto interleave_reads = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < TM + TN; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                       // one DS read
-      __builtin_amdgcn_sched_group_barrier(0x008, (TM * TN) / (TM + TN), 0);   // a share of the MFMAs
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one DS read
     }
+    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
   };
 
   load_a(0, Set0{});

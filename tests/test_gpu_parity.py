@@ -109,3 +109,78 @@ def test_full_size_configs(name):
     cfg = get_config(name)
     _, gpu, x, w = run_layer(cfg)
     compare_layer(cfg, gpu, x, w)
+
+
+def _step_run(cfg, n_steps, tracked, all_steps):
+    """Runs n_steps of rom_step on all sequences; the oracle follows `tracked` sequences through
+    every step and all sequences through the first `all_steps` steps."""
+    from gpu_util import f64_weights
+    from paper_2506_18145_amd import RomLayer
+    from rom_synth import make_step_inputs
+    w = make_weights(cfg)
+    w64 = f64_weights(w)
+    xs = make_step_inputs(cfg, n_steps)                      # [n_steps, B, d_model]
+    cs0, ss0 = make_states(cfg)
+    layer = RomLayer(cfg, w)
+    cs, ss = layer.to_device(cs0, typed=False), layer.to_device(ss0, typed=False)
+    xs_d = layer.to_device(xs)
+    B = cfg.batch
+    ref_cs, ref_ss = cs0[tracked].astype(np.float64), ss0[tracked].astype(np.float64)
+    all_cs, all_ss = cs0.astype(np.float64), ss0.astype(np.float64)
+    worst, excluded = 0.0, 0
+    tol = TOL[cfg.dtype]
+    for t in range(n_steps):
+        out = layer.step(xs_d[t], cs, ss)
+        torch.cuda.synchronize()
+        idx = to_np(layer.ws_view("expert_idx", B, 1))
+        got = to_np(out)
+        if t < all_steps:
+            gpu = {k: to_np(layer.ws_view(k, B, 1)) for k in
+                   ("expert_idx", "gate", "counts", "offsets", "perm", "inv_perm", "logits")}
+            _, n_excl = check_routing(cfg, gpu, xs[t], w)
+            excluded += n_excl
+            ref = O.rom_step(xs[t], w64, cfg.top_k, cfg.gate_mode, all_cs, all_ss, expert_idx=idx)
+            all_cs, all_ss = ref["conv_state"], ref["ssm_state"]
+            assert rel_err(got, ref["out"]) <= tol, f"step {t} (all sequences)"
+            assert rel_err(to_np(ss), all_ss) <= tol and rel_err(to_np(cs), all_cs) <= tol
+        # tracked sequences: routing must agree outside the margin band, floats within tolerance
+        logits = O.router_logits(xs[t][tracked], w64["w_router"], w64.get("b_router"))
+        own = O.topk_select(logits, cfg.top_k)
+        close = O.topk_margin(logits, cfg.top_k) < 1e-5
+        assert np.array_equal(idx[tracked][~close], own[~close]), f"step {t}: routing differs"
+        ref = O.rom_step(xs[t][tracked], w64, cfg.top_k, cfg.gate_mode, ref_cs, ref_ss,
+                         expert_idx=idx[tracked])
+        ref_cs, ref_ss = ref["conv_state"], ref["ssm_state"]
+        err = rel_err(got[tracked], ref["out"])
+        worst = max(worst, err)
+        assert err <= tol, f"step {t}: out error {err:.3e}"
+    assert rel_err(to_np(ss)[tracked], ref_ss) <= tol
+    assert rel_err(to_np(cs)[tracked], ref_cs) <= tol
+    print(f"[{cfg.name} step x{n_steps}] worst out error {worst:.2e}, excluded in full-batch steps {excluded}",
+          flush=True)
+
+
+def test_step_small():
+    cfg = small_cfg(batch=37, seq_len=40, top_k=2, gate_mode=1, step=True)
+    _step_run(cfg, 40, tracked=list(range(37)), all_steps=3)
+
+
+def test_step_matches_forward_last_token():
+    """forward(L) followed by one rom_step equals forward(L+1) on its last token."""
+    cfg = small_cfg(batch=3, seq_len=65)
+    from paper_2506_18145_amd import RomLayer
+    w, x = make_weights(cfg), make_input(cfg)
+    layer = RomLayer(cfg, w)
+    xd = layer.to_device(x)
+    full = layer.forward(xd)
+    head, cs, ss = layer.forward(xd[:, :-1].contiguous(), return_states=True)
+    last = layer.step(xd[:, -1].contiguous(), cs, ss)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(last), to_np(full[:, -1])) <= TOL["bf16"] * 0.25
+
+
+def test_step_cfg4_decode_512_steps():
+    """256 sequences x 512 consecutive steps; the oracle tracks two sequences through all steps and
+    every sequence through the first four."""
+    cfg = get_config("cfg4")
+    _step_run(cfg, 512, tracked=[3, 200], all_steps=4)
