@@ -22,6 +22,9 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # plain-ALU ceiling for fp32: 256 CUs x 4 SIMDs x 16 lanes x 2 flop (FMA) x 2.4 GHz, no packed math
 PEAK_ALU_FP32_TFLOPS = 78.6
+# HBM bytes per in_proj launch at cfg2 from rocprofv3 FETCH_SIZE (x2.0 copy-kernel calibration) +
+# WRITE_SIZE (x1.0): see profiles/forward_cfg2_hbm_traffic.md
+TRAFFIC_IN_PROJ_CFG2_BYTES = (994 + 257) * 2 ** 20
 
 
 def stage_model(cfg):
@@ -76,6 +79,9 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (a kernel of known traffic, for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -120,6 +126,13 @@ def main():
     torch.cuda.synchronize()
     elapsed_plain = time.perf_counter() - t1
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     ms_per_step = elapsed * 1e3 / args.steps
     n_tok = B * L
     model = stage_model(cfg)
@@ -139,7 +152,8 @@ def main():
     dom = stages["in_proj"]
     roofline = {"kernel": "in_proj grouped GEMM (gemm_bf16_mfma_kernel)", "bound": "mfma",
                 "achieved": dom.get("achieved_tflops"), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": dom.get("frac"), "traffic": None}
+                "frac": dom.get("frac"),
+                "traffic": TRAFFIC_IN_PROJ_CFG2_BYTES if cfg.name == "cfg2" else None}
 
     result = {
         "metric": "RoM layer fwd tokens/s at d=2048,L=16K; % MFMA peak (GEMM), % HBM BW (scan)",
