@@ -303,25 +303,51 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
 
   // epilogue.  The weight fragment is the MFMA's row operand, so a lane holds, for ONE output row
   // (tile row lane%32), the output columns 8*q + 4*(lane/32) + r of each 32-wide tile in
-  // accumulator element 4*q + r: four consecutive columns per q, stored as one 8/16-byte write.
+  // accumulator element 4*q + r: four consecutive columns per q.
+  if constexpr (EPI == kEpiPlainF32) {
+    // fp32 output: one 16-byte store per q straight from the accumulators
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int64_t p = tc.row0 + wm * WTM + i * 32 + frag_row;
-    const bool row_ok = p < tc.row_end;
-    const int64_t crow = row_ok ? (a.c_rows ? a.c_rows[p] : p) : 0;
-    float scale = 1.0f;
-    if (EPI == kEpiRowScale) scale = row_ok ? a.row_scale[crow] : 0.0f;
+    for (int i = 0; i < TM; ++i) {
+      const int64_t p = tc.row0 + wm * WTM + i * 32 + frag_row;
+      const bool row_ok = p < tc.row_end;
+      const int64_t crow = row_ok ? (a.c_rows ? a.c_rows[p] : p) : 0;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+      for (int j = 0; j < TN; ++j) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int col = tc.n0 + wn * WTN + j * 32 + q * 8 + frag_half * 4;
-        float v[4];
+        for (int q = 0; q < 4; ++q) {
+          const int col = tc.n0 + wn * WTN + j * 32 + q * 8 + frag_half * 4;
+          if (row_ok && col < a.N)
+            *reinterpret_cast<float4 *>(static_cast<float *>(a.C) + crow * a.ldc + col) =
+                make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        }
+      }
+    }
+  } else {
+    // bf16 output: every wave parks its sub-tile (after bias / softplus / row scale) in its own
+    // slice of the now idle LDS, then writes it out row by row, 16 bytes per lane, so that each
+    // store instruction covers whole 128..256-byte row segments.  No workgroup barrier is needed:
+    // after the last slab's barrier nobody reads the operand buffers for real any more.
+    constexpr int kPitch = WTN * 2 + 16;                 // bytes per parked row (16-byte aligned)
+    char *stage = reinterpret_cast<char *>(smem) + wave * (WTM * kPitch);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
-        if (row_ok && col < a.N) {
+    for (int i = 0; i < TM; ++i) {
+      float scale = 1.0f;
+      if (EPI == kEpiRowScale) {
+        const int64_t p = tc.row0 + wm * WTM + i * 32 + frag_row;
+        scale = p < tc.row_end ? a.row_scale[a.c_rows ? a.c_rows[p] : p] : 0.0f;
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int lcol = j * 32 + q * 8 + frag_half * 4;
+          float v[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
           if (EPI == kEpiBiasSoftplus) {
-            const float4 b4 = *reinterpret_cast<const float4 *>(a.bias + col);
+            const int col = tc.n0 + wn * WTN + lcol;
+            float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (col < a.N) b4 = *reinterpret_cast<const float4 *>(a.bias + col);
             v[0] = softplus_fast(v[0] + b4.x); v[1] = softplus_fast(v[1] + b4.y);
             v[2] = softplus_fast(v[2] + b4.z); v[3] = softplus_fast(v[3] + b4.w);
           }
@@ -329,16 +355,25 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[r] *= scale;
           }
-          if (EPI == kEpiPlainF32) {
-            *reinterpret_cast<float4 *>(static_cast<float *>(a.C) + crow * a.ldc + col) =
-                make_float4(v[0], v[1], v[2], v[3]);
-          } else {
-            uint2 pk;
-            pk.x = static_cast<unsigned int>(f32_to_bf16(v[0])) | (static_cast<unsigned int>(f32_to_bf16(v[1])) << 16);
-            pk.y = static_cast<unsigned int>(f32_to_bf16(v[2])) | (static_cast<unsigned int>(f32_to_bf16(v[3])) << 16);
-            *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(a.C) + crow * a.ldc + col) = pk;
-          }
+          uint2 pk;
+          pk.x = pack_bf16x2(v[0], v[1]);
+          pk.y = pack_bf16x2(v[2], v[3]);
+          *reinterpret_cast<uint2 *>(stage + (i * 32 + frag_row) * kPitch + lcol * 2) = pk;
         }
+      }
+    }
+    constexpr int kChunks = WTN / 8;                     // 16-byte chunks per parked row
+    constexpr int kRowsPerPass = 64 / kChunks;
+    const int chunk = lane % kChunks, sub = lane / kChunks;
+    const int col = tc.n0 + wn * WTN + chunk * 8;
+#pragma unroll 4
+    for (int r0 = 0; r0 < WTM; r0 += kRowsPerPass) {
+      const int row = r0 + sub;
+      const int64_t p = tc.row0 + wm * WTM + row;
+      if (p < tc.row_end && col < a.N) {
+        const int64_t crow = a.c_rows ? a.c_rows[p] : p;
+        const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * kPitch + chunk * 16);
+        *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.C) + crow * a.ldc + col) = v;
       }
     }
   }
@@ -406,7 +441,9 @@ int grid_tiles(const GemmArgs &a, int BM, int BN) {
 
 template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL>
 hipError_t launch_mfma_k(const GemmArgs &a, hipStream_t s) {
-  constexpr int kSmem = 2 * (BM + BN) * kRowChunks * 16;
+  constexpr int kLoopSmem = 2 * (BM + BN) * kRowChunks * 16;
+  constexpr int kStageSmem = EPI == kEpiPlainF32 ? 0 : BM * WN * ((BN / WN) * 2 + 16);
+  constexpr int kSmem = kLoopSmem > kStageSmem ? kLoopSmem : kStageSmem;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(
@@ -428,7 +465,9 @@ hipError_t launch_mfma(const GemmArgs &a, hipStream_t s) {
 template <int EPI>
 hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
   const int64_t rows_per_group = a.M / (a.n_groups > 0 ? a.n_groups : 1);
-  if (rows_per_group >= 1024 && a.N >= 256) return launch_mfma<256, 256, 2, 2, EPI>(a, s);
+  // a short inner dimension makes the launch epilogue-bound: smaller tiles put several
+  // workgroups on a CU so that loads, MFMAs and stores of different tiles overlap
+  if (rows_per_group >= 1024 && a.N >= 256 && a.K > 256) return launch_mfma<256, 256, 2, 2, EPI>(a, s);
   if (rows_per_group >= 96) return launch_mfma<128, 128, 2, 2, EPI>(a, s);
   return launch_mfma<64, 128, 2, 2, EPI>(a, s);
 }
@@ -437,8 +476,9 @@ hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
 
 hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
-  const bool mfma_ok = a.dtype == ROM_DTYPE_BF16 && a.K % 8 == 0 && a.lda % 8 == 0 && a.N % 4 == 0 &&
-                       a.ldc % 4 == 0 && (reinterpret_cast<uintptr_t>(a.A) % 16 == 0) &&
+  const int out_align = a.c_is_f32 ? 4 : 8;      // elements per output store
+  const bool mfma_ok = a.dtype == ROM_DTYPE_BF16 && a.K % 8 == 0 && a.lda % 8 == 0 &&
+                       a.N % out_align == 0 && a.ldc % out_align == 0 && (reinterpret_cast<uintptr_t>(a.A) % 16 == 0) &&
                        (reinterpret_cast<uintptr_t>(a.W) % 16 == 0) &&
                        (reinterpret_cast<uintptr_t>(a.C) % 16 == 0) && a.a_span < (1ll << 32) &&
                        static_cast<int64_t>(a.N) * a.K < (1ll << 32) &&

@@ -13,11 +13,15 @@ typedef unsigned short bf16_t;  // raw bf16 bit pattern
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) {
   return __uint_as_float(static_cast<unsigned int>(v) << 16);
 }
-// round-to-nearest-even; inputs are finite
+typedef __bf16 hw_bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float hw_f32x2_t __attribute__((ext_vector_type(2)));
+// two floats -> packed bf16 pair (lo in bits 0..15), round-to-nearest-even: one v_cvt_pk_bf16_f32
+__device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {
+  const hw_f32x2_t f = {lo, hi};
+  return __builtin_bit_cast(unsigned int, __builtin_convertvector(f, hw_bf16x2_t));
+}
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  unsigned int u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return static_cast<bf16_t>(u >> 16);
+  return static_cast<bf16_t>(pack_bf16x2(f, 0.0f) & 0xFFFFu);
 }
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }

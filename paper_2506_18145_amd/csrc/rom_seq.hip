@@ -20,8 +20,7 @@ template <> struct Chunk<bf16_t> {
     return __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16));
   }
   __device__ __forceinline__ void set_pair(int i, float lo, float hi) {   // elements 2i, 2i+1
-    (&raw.x)[i] = static_cast<unsigned int>(f32_to_bf16(lo)) |
-                  (static_cast<unsigned int>(f32_to_bf16(hi)) << 16);
+    (&raw.x)[i] = pack_bf16x2(lo, hi);
   }
 };
 template <> struct Chunk<float> {
@@ -389,8 +388,8 @@ __global__ __launch_bounds__(256) void scan_gate_kernel(
         const float4 v = *reinterpret_cast<const float4 *>(&sm.g[buf][r][q]);
         if (sizeof(T) == 2) {
           uint2 pk;
-          pk.x = static_cast<unsigned int>(f32_to_bf16(v.x)) | (static_cast<unsigned int>(f32_to_bf16(v.y)) << 16);
-          pk.y = static_cast<unsigned int>(f32_to_bf16(v.z)) | (static_cast<unsigned int>(f32_to_bf16(v.w)) << 16);
+          pk.x = pack_bf16x2(v.x, v.y);
+          pk.y = pack_bf16x2(v.z, v.w);
           *reinterpret_cast<uint2 *>(g_b + t * d_inner + q) = pk;
         } else {
           *reinterpret_cast<float4 *>(g_b + t * d_inner + q) = v;
