@@ -467,7 +467,7 @@ hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
   const int64_t rows_per_group = a.M / (a.n_groups > 0 ? a.n_groups : 1);
   // a short inner dimension makes the launch epilogue-bound: smaller tiles put several
   // workgroups on a CU so that loads, MFMAs and stores of different tiles overlap
-  if (rows_per_group >= 1024 && a.N >= 256 && a.K > 256) return launch_mfma<256, 256, 2, 2, EPI>(a, s);
+  if (rows_per_group >= 1024 && a.N >= 256 && a.K > 256) return launch_mfma<256, 256, 4, 2, EPI>(a, s);
   if (rows_per_group >= 96) return launch_mfma<128, 128, 2, 2, EPI>(a, s);
   return launch_mfma<64, 128, 2, 2, EPI>(a, s);
 }
