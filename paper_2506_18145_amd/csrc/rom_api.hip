@@ -13,7 +13,7 @@ constexpr size_t kNone = static_cast<size_t>(-1);
 struct Plan {                 // byte offsets inside the workspace
   size_t total;
   size_t expert_idx, gate, counts, offsets, perm, inv_perm, tok_of_pos, block_counts, logits;
-  size_t xz, xz_sorted, u, xdbl, dt_low, bc, dt, dt_raw, g, op_sorted, conv_tmp;
+  size_t xz, xz_sorted, u, xdbl, dt_low, bc, dt, dt_raw, g, op_sorted, conv_tmp, scan_q, scan_p;
 };
 
 int check_dims(const rom_dims *d) {
@@ -75,6 +75,8 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   p.g = take(N * De * b);
   p.op_sorted = multi ? take(S * Dm * b) : kNone;
   p.conv_tmp = take(static_cast<size_t>(n_seq) * De * 3 * 4);
+  p.scan_q = take(scan_chunk_state_bytes(n_seq, seq_len, d->d_inner));
+  p.scan_p = take(scan_chunk_state_bytes(n_seq, seq_len, d->d_inner));
   p.total = off;
   return p;
 }
@@ -226,7 +228,8 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   // selective scan + D skip + SiLU(z) gate, Eq. (5), (6)
   const char *z = static_cast<const char *>(at(p.xz)) + static_cast<size_t>(De) * eb;
   ROM_TRY(launch_scan_gate(d->dtype, at(p.u), at(p.dt), static_cast<const float *>(at(p.bc)), z, 2 * De,
-                           w->A_log, w->D, ssm_in, ssm_out, at(p.g), B, L, De, s));
+                           w->A_log, w->D, ssm_in, ssm_out, at(p.g), B, L, De,
+                           static_cast<float *>(at(p.scan_q)), static_cast<float *>(at(p.scan_p)), s));
   mark.done(ROM_STAGE_SCAN);
 
   // out projection, Eq. (13), and the gate-weighted combine, Eq. (12)

@@ -83,9 +83,12 @@ hipError_t launch_split_xdbl(int dtype, const float *xdbl, const int32_t *inv_pe
 hipError_t launch_conv_silu(int dtype, const void *xz, int64_t ld_xz, const float *conv_w,
                             const float *conv_b, const float *state_in, float *state_out, void *u,
                             int64_t B, int64_t L, int d_inner, hipStream_t s);
+// chunk_q / chunk_p: f32 scratch of scan_chunk_state_bytes() each (chunk end states and decays)
+size_t scan_chunk_state_bytes(int64_t B, int64_t L, int d_inner);
 hipError_t launch_scan_gate(int dtype, const void *u, const void *dt, const float *bc, const void *z,
                             int64_t ld_z, const float *A_log, const float *D, const float *h_in,
-                            float *h_out, void *g, int64_t B, int64_t L, int d_inner, hipStream_t s);
+                            float *h_out, void *g, int64_t B, int64_t L, int d_inner, float *chunk_q,
+                            float *chunk_p, hipStream_t s);
 // out[n, :] = sum_k gate[n*K+k] * op[inv_perm[n*K+k], :]
 hipError_t launch_combine(int dtype, const void *op, const int32_t *inv_perm, const float *gate,
                           void *out, int64_t n_tokens, int top_k, int d_model, hipStream_t s);

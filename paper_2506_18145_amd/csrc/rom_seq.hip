@@ -153,22 +153,26 @@ __global__ __launch_bounds__(256) void conv_silu_kernel(
 
 // ------------------------------------------------------------------ selective scan, Eq. (5)
 // Lane = (channel, state): 16 lanes share a channel, a 256-thread block owns 16 channels of one
-// sequence and walks the whole sequence once; the 16 states of a channel live in registers, one
-// per lane, so the recurrence needs no second pass and no carry fix-up.
+// sequence chunk and walks it once; the 16 states of a channel live in registers, one per lane.
 // Work is cut into tiles of kScanTile steps and groups of 16 steps:
 //   * the block fetches a tile of dt, u, z (16 channels wide) and of B_t, C_t with 8/16-byte
-//     loads one tile ahead of use (registers), then parks it in double-buffered LDS as floats;
+//     loads one tile ahead of use (registers), then parks it in double-buffered LDS;
 //     B/C are stored transposed so that lane n reads B_{t,n}, C_{t,n} of four steps at once;
 //   * lane n of a channel picks up dt, u, z of step n of a group and hands dt and dt*u round
 //     with DPP row broadcasts;
 //   * the 16 products C_n*h_n of 16 steps are summed by a transposing butterfly (15 DPP adds per
 //     step pair instead of a full reduction per step) that leaves y of step n in lane n, which
 //     then applies the D skip and the SiLU(z) gate; g leaves through LDS in 4-channel packets.
+// A single wavefront per SIMD issues plain ALU instructions at well under half rate, and one
+// sequence of 4096 channels is exactly one wavefront per SIMD.  Short batches are therefore cut
+// into n_chunks time chunks: a state-only pass (kStateOnly: no C, z, reduction or output) runs
+// every chunk but the last from a zero state and leaves its end state q and total decay
+// P = exp(A * sum dt); the full pass then starts chunk c from the fold h <- P_k h + q_k over the
+// chunks before it.  The recurrence is linear in h, so this is the same arithmetic regrouped.
 constexpr int kScanTile = 64;
 constexpr int kScanGroups = kScanTile / 16;
 constexpr int kScanCh = 16;
 constexpr int kBcPitch = kScanTile + 4;     // floats; keeps 16-byte alignment of the row reads
-constexpr int kChPitch = kScanCh + 4;       // floats per step row of the dt/u/z/g tiles
 
 template <int CTRL> __device__ __forceinline__ float dpp(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
@@ -179,12 +183,15 @@ constexpr int kDppHalfMirror = 0x141;   // lane i <-> 7 - i inside each 8
 constexpr int kDppRowMirror = 0x140;    // lane i <-> 15 - i inside each 16
 constexpr int kDppRowBcast0 = 0x150;    // row_newbcast:0 (+j for lane j of the row)
 
-struct __attribute__((aligned(16))) ScanSmem {
-  float dt[2][kScanTile][kChPitch];
-  float u[2][kScanTile][kChPitch];
-  float z[2][kScanTile][kChPitch];
+// elements per step row of the dt/u/z/g tiles (16 channels + padding that keeps rows 16-byte aligned)
+template <typename T> struct ScanPitch { static constexpr int v = kScanCh + 16 / sizeof(T); };
+
+template <typename T> struct __attribute__((aligned(16))) ScanSmem {
+  T dt[2][kScanTile][ScanPitch<T>::v];
+  T u[2][kScanTile][ScanPitch<T>::v];
+  T z[2][kScanTile][ScanPitch<T>::v];
   float bc[2][32][kBcPitch];            // [buffer][B_0..B_15, C_0..C_15][step]
-  float g[2][kScanTile][kChPitch];
+  T g[2][kScanTile][ScanPitch<T>::v];
 };
 
 template <int J> struct StepSeq {
@@ -232,25 +239,29 @@ __device__ __forceinline__ float transpose_reduce16(const float *hs, const float
   return hi1 ? hi : lo;
 }
 
+// sum of v over the 16 lanes of a row, in every lane
+__device__ __forceinline__ float row_sum16(float v) {
+#pragma clang fp contract(off)
+  v = dpp<kDppRowMirror>(v) + v;
+  v = dpp<kDppHalfMirror>(v) + v;
+  v = dpp<kDppQuadRev>(v) + v;
+  v = dpp<kDppQuadXor1>(v) + v;
+  return v;
+}
+
 // N consecutive elements of T held in registers
 template <typename T, int N> struct Pack;
 template <> struct Pack<bf16_t, 8> {
   uint4 raw;
   __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const uint4 *>(p); }
+  __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<uint4 *>(p) = raw; }
   __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
-  __device__ __forceinline__ float get(int i) const {
-    const unsigned int w = (&raw.x)[i >> 1];
-    return __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16));
-  }
 };
 template <> struct Pack<bf16_t, 4> {
   uint2 raw;
   __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const uint2 *>(p); }
+  __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<uint2 *>(p) = raw; }
   __device__ __forceinline__ void zero() { raw = make_uint2(0, 0); }
-  __device__ __forceinline__ float get(int i) const {
-    const unsigned int w = (&raw.x)[i >> 1];
-    return __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16));
-  }
 };
 template <> struct Pack<float, 8> {
   float4 lo, hi;
@@ -258,69 +269,76 @@ template <> struct Pack<float, 8> {
     lo = *reinterpret_cast<const float4 *>(p);
     hi = *reinterpret_cast<const float4 *>(p + 4);
   }
+  __device__ __forceinline__ void store(float *p) const {
+    *reinterpret_cast<float4 *>(p) = lo;
+    *reinterpret_cast<float4 *>(p + 4) = hi;
+  }
   __device__ __forceinline__ void zero() { lo = make_float4(0.f, 0.f, 0.f, 0.f); hi = lo; }
-  __device__ __forceinline__ float get(int i) const { return i < 4 ? (&lo.x)[i] : (&hi.x)[i - 4]; }
 };
 template <> struct Pack<float, 4> {
   float4 raw;
   __device__ __forceinline__ void load(const float *p) { raw = *reinterpret_cast<const float4 *>(p); }
+  __device__ __forceinline__ void store(float *p) const { *reinterpret_cast<float4 *>(p) = raw; }
   __device__ __forceinline__ void zero() { raw = make_float4(0.f, 0.f, 0.f, 0.f); }
-  __device__ __forceinline__ float get(int i) const { return (&raw.x)[i]; }
 };
 
 // One thread's share of a tile: 8 channels of one step of dt (threads 0..127) or u (128..255),
-// 4 channels of one step of z, 8 of the 32 B/C values of one step.
+// 4 channels of one step of z, 8 of the 32 B/C values of one step (the state-only pass takes
+// neither z nor C).
 template <typename T> struct ScanStage {
   Pack<T, 8> du;
   Pack<T, 4> z;
   float4 bc0, bc1;
 };
 
-template <typename T, bool kTail>
+template <typename T, bool kStateOnly, bool kTail>
 __device__ __forceinline__ void scan_fetch(ScanStage<T> &r, const T *dt_b, const T *u_b, const T *z_b,
-                                           const float *bc_b, int64_t t0, int64_t L, int d_inner,
+                                           const float *bc_b, int64_t t0, int64_t t_end, int d_inner,
                                            int64_t ld_z, int tid) {
   const int64_t t_du = t0 + ((tid & 127) >> 1);
-  if (!kTail || t_du < L) r.du.load((tid < 128 ? dt_b : u_b) + t_du * d_inner + (tid & 1) * 8);
+  if (!kTail || t_du < t_end) r.du.load((tid < 128 ? dt_b : u_b) + t_du * d_inner + (tid & 1) * 8);
   else r.du.zero();
   const int64_t t_z = t0 + (tid >> 2);
-  if (!kTail || t_z < L) {
-    r.z.load(z_b + t_z * ld_z + (tid & 3) * 4);
-    const float4 *src = reinterpret_cast<const float4 *>(bc_b + t_z * 32 + (tid & 3) * 8);
-    r.bc0 = src[0];
-    r.bc1 = src[1];
+  const bool want_bc = !kStateOnly || (tid & 3) < 2;
+  if (!kTail || t_z < t_end) {
+    if (!kStateOnly) r.z.load(z_b + t_z * ld_z + (tid & 3) * 4);
+    if (want_bc) {
+      const float4 *src = reinterpret_cast<const float4 *>(bc_b + t_z * 32 + (tid & 3) * 8);
+      r.bc0 = src[0];
+      r.bc1 = src[1];
+    }
   } else {
-    r.z.zero();
+    if (!kStateOnly) r.z.zero();
     r.bc0 = make_float4(0.f, 0.f, 0.f, 0.f);
     r.bc1 = r.bc0;
   }
 }
 
-template <typename T>
-__device__ __forceinline__ void scan_park(ScanSmem &sm, int buf, const ScanStage<T> &r, int tid) {
-  {
-    float *dst = (tid < 128 ? &sm.dt[buf][0][0] : &sm.u[buf][0][0]) + ((tid & 127) >> 1) * kChPitch +
-                 (tid & 1) * 8;
-    *reinterpret_cast<float4 *>(dst) = make_float4(r.du.get(0), r.du.get(1), r.du.get(2), r.du.get(3));
-    *reinterpret_cast<float4 *>(dst + 4) = make_float4(r.du.get(4), r.du.get(5), r.du.get(6), r.du.get(7));
-  }
+template <typename T, bool kStateOnly>
+__device__ __forceinline__ void scan_park(ScanSmem<T> &sm, int buf, const ScanStage<T> &r, int tid) {
+  r.du.store((tid < 128 ? &sm.dt[buf][0][0] : &sm.u[buf][0][0]) + ((tid & 127) >> 1) * ScanPitch<T>::v +
+             (tid & 1) * 8);
   const int row = tid >> 2, part = tid & 3;
-  *reinterpret_cast<float4 *>(&sm.z[buf][row][part * 4]) =
-      make_float4(r.z.get(0), r.z.get(1), r.z.get(2), r.z.get(3));
-  const int col = part * 8;
-  sm.bc[buf][col + 0][row] = r.bc0.x; sm.bc[buf][col + 1][row] = r.bc0.y;
-  sm.bc[buf][col + 2][row] = r.bc0.z; sm.bc[buf][col + 3][row] = r.bc0.w;
-  sm.bc[buf][col + 4][row] = r.bc1.x; sm.bc[buf][col + 5][row] = r.bc1.y;
-  sm.bc[buf][col + 6][row] = r.bc1.z; sm.bc[buf][col + 7][row] = r.bc1.w;
+  if (!kStateOnly) r.z.store(&sm.z[buf][row][part * 4]);
+  if (!kStateOnly || part < 2) {
+    const int col = part * 8;
+    sm.bc[buf][col + 0][row] = r.bc0.x; sm.bc[buf][col + 1][row] = r.bc0.y;
+    sm.bc[buf][col + 2][row] = r.bc0.z; sm.bc[buf][col + 3][row] = r.bc0.w;
+    sm.bc[buf][col + 4][row] = r.bc1.x; sm.bc[buf][col + 5][row] = r.bc1.y;
+    sm.bc[buf][col + 6][row] = r.bc1.z; sm.bc[buf][col + 7][row] = r.bc1.w;
+  }
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void scan_gate_kernel(
+// grid: (d_inner / 16, B, chunks handled by this pass).  chunk_q / chunk_p: f32
+// [B][n_chunks - 1][d_inner][16], end state from zero and total decay of every chunk but the last.
+template <typename T, bool kStateOnly>
+__global__ __launch_bounds__(256) void scan_kernel(
     const T *__restrict__ u, const T *__restrict__ dt, const float *__restrict__ bc,
     const T *__restrict__ z, int64_t ld_z, const float *__restrict__ A_log,
     const float *__restrict__ D, const float *__restrict__ h_in, float *__restrict__ h_out,
-    T *__restrict__ g, int64_t L, int d_inner) {
-  __shared__ ScanSmem sm;
+    T *__restrict__ g, int64_t L, int d_inner, int64_t chunk_len, int n_chunks,
+    float *__restrict__ chunk_q, float *__restrict__ chunk_p) {
+  __shared__ ScanSmem<T> sm;
   const int tid = threadIdx.x;
   const int n = tid & 15;            // state index = lane inside the DPP row
   const int cl = tid >> 4;           // channel inside the block
@@ -332,72 +350,93 @@ __global__ __launch_bounds__(256) void scan_gate_kernel(
   const int c0 = grp * kScanCh;
   const int ch = c0 + cl;
   const int64_t b = blockIdx.y;
+  const int chunk = blockIdx.z;
+  const int64_t t_begin = chunk * chunk_len;
+  const int64_t t_end = (t_begin + chunk_len < L) ? t_begin + chunk_len : L;
 
   const float a2 = -__expf(A_log[static_cast<int64_t>(ch) * 16 + n]) * 1.44269504088896341f;
-  const float d_skip = D[ch];
-  float h = h_in ? h_in[(b * d_inner + ch) * 16 + n] : 0.0f;
+  const float d_skip = kStateOnly ? 0.0f : D[ch];
+  float h = 0.0f;
+  if (!kStateOnly) {
+    h = h_in ? h_in[(b * d_inner + ch) * 16 + n] : 0.0f;
+    for (int k = 0; k < chunk; ++k) {      // fold the chunks before this one
+      const int64_t at = ((b * (n_chunks - 1) + k) * d_inner + ch) * 16 + n;
+      h = fmaf(chunk_p[at], h, chunk_q[at]);
+    }
+  }
+  float dt_sum = 0.0f;
 
   const T *u_b = u + b * L * d_inner + c0;
   const T *dt_b = dt + b * L * d_inner + c0;
-  const T *z_b = z + b * L * ld_z + c0;
+  const T *z_b = kStateOnly ? nullptr : z + b * L * ld_z + c0;
   const float *bc_b = bc + b * L * 32;
-  T *g_b = g + b * L * d_inner + c0;
+  T *g_b = kStateOnly ? nullptr : g + b * L * d_inner + c0;
 
   ScanStage<T> st;
-  const int64_t n_tiles = (L + kScanTile - 1) / kScanTile;
-  if (L >= kScanTile) scan_fetch<T, false>(st, dt_b, u_b, z_b, bc_b, 0, L, d_inner, ld_z, tid);
-  else scan_fetch<T, true>(st, dt_b, u_b, z_b, bc_b, 0, L, d_inner, ld_z, tid);
-  scan_park<T>(sm, 0, st, tid);
+  const int64_t n_tiles = (t_end - t_begin + kScanTile - 1) / kScanTile;
+  if (t_begin + kScanTile <= t_end)
+    scan_fetch<T, kStateOnly, false>(st, dt_b, u_b, z_b, bc_b, t_begin, t_end, d_inner, ld_z, tid);
+  else
+    scan_fetch<T, kStateOnly, true>(st, dt_b, u_b, z_b, bc_b, t_begin, t_end, d_inner, ld_z, tid);
+  scan_park<T, kStateOnly>(sm, 0, st, tid);
   __syncthreads();
 
   for (int64_t ti = 0; ti < n_tiles; ++ti) {
     const int buf = static_cast<int>(ti & 1);
-    const int64_t t0 = ti * kScanTile;
+    const int64_t t0 = t_begin + ti * kScanTile;
     const bool has_next = ti + 1 < n_tiles;
     if (has_next) {     // next tile's inputs travel while this tile is computed
-      if (t0 + 2 * kScanTile <= L)
-        scan_fetch<T, false>(st, dt_b, u_b, z_b, bc_b, t0 + kScanTile, L, d_inner, ld_z, tid);
+      if (t0 + 2 * kScanTile <= t_end)
+        scan_fetch<T, kStateOnly, false>(st, dt_b, u_b, z_b, bc_b, t0 + kScanTile, t_end, d_inner, ld_z, tid);
       else
-        scan_fetch<T, true>(st, dt_b, u_b, z_b, bc_b, t0 + kScanTile, L, d_inner, ld_z, tid);
+        scan_fetch<T, kStateOnly, true>(st, dt_b, u_b, z_b, bc_b, t0 + kScanTile, t_end, d_inner, ld_z, tid);
     }
 #pragma unroll
     for (int gi = 0; gi < kScanGroups; ++gi) {
       const int s0 = gi * 16;
-      const float dt_r = sm.dt[buf][s0 + n][cl];
-      const float u_r = sm.u[buf][s0 + n][cl];
-      const float z_r = sm.z[buf][s0 + n][cl];
+      const float dt_r = to_f32(sm.dt[buf][s0 + n][cl]);
+      const float u_r = to_f32(sm.u[buf][s0 + n][cl]);
       const float dtu_r = dt_r * u_r;
-      float bv[16], cv[16], hs[16];
+      float bv[16], hs[16];
 #pragma unroll
       for (int j = 0; j < 16; j += 4) {
         const float4 b4 = *reinterpret_cast<const float4 *>(&sm.bc[buf][n][s0 + j]);
-        const float4 c4 = *reinterpret_cast<const float4 *>(&sm.bc[buf][16 + n][s0 + j]);
         bv[j] = b4.x; bv[j + 1] = b4.y; bv[j + 2] = b4.z; bv[j + 3] = b4.w;
-        cv[j] = c4.x; cv[j + 1] = c4.y; cv[j + 2] = c4.z; cv[j + 3] = c4.w;
       }
       StepSeq<15>::run(dt_r, dtu_r, a2, bv, h, hs);
-      const float y = transpose_reduce16(hs, cv, n) + d_skip * u_r;
-      sm.g[buf][s0 + n][cl] = y * silu_f32(z_r);
+      if (kStateOnly) {
+        dt_sum += dt_r;
+      } else {
+        float cv[16];
+#pragma unroll
+        for (int j = 0; j < 16; j += 4) {
+          const float4 c4 = *reinterpret_cast<const float4 *>(&sm.bc[buf][16 + n][s0 + j]);
+          cv[j] = c4.x; cv[j + 1] = c4.y; cv[j + 2] = c4.z; cv[j + 3] = c4.w;
+        }
+        const float z_r = to_f32(sm.z[buf][s0 + n][cl]);
+        const float y = transpose_reduce16(hs, cv, n) + d_skip * u_r;
+        sm.g[buf][s0 + n][cl] = from_f32<T>(y * silu_f32(z_r));
+      }
     }
-    if (has_next) scan_park<T>(sm, buf ^ 1, st, tid);
+    if (has_next) scan_park<T, kStateOnly>(sm, buf ^ 1, st, tid);
     __syncthreads();
-    {   // g of this tile: thread -> (step row, 4 channels)
+    if (!kStateOnly) {   // g of this tile: thread -> (step row, 4 channels)
       const int r = tid >> 2, q = (tid & 3) * 4;
       const int64_t t = t0 + r;
-      if (t < L) {
-        const float4 v = *reinterpret_cast<const float4 *>(&sm.g[buf][r][q]);
-        if (sizeof(T) == 2) {
-          uint2 pk;
-          pk.x = pack_bf16x2(v.x, v.y);
-          pk.y = pack_bf16x2(v.z, v.w);
-          *reinterpret_cast<uint2 *>(g_b + t * d_inner + q) = pk;
-        } else {
-          *reinterpret_cast<float4 *>(g_b + t * d_inner + q) = v;
-        }
+      if (t < t_end) {
+        Pack<T, 4> pk;
+        pk.load(&sm.g[buf][r][q]);
+        pk.store(g_b + t * d_inner + q);
       }
     }
   }
-  if (h_out) h_out[(b * d_inner + ch) * 16 + n] = h;
+  if (kStateOnly) {
+    const int64_t at = ((b * (n_chunks - 1) + chunk) * d_inner + ch) * 16 + n;
+    chunk_q[at] = h;
+    chunk_p[at] = fast_exp2(a2 * row_sum16(dt_sum));
+  } else if (h_out && chunk == n_chunks - 1) {
+    h_out[(b * d_inner + ch) * 16 + n] = h;
+  }
 }
 
 // ------------------------------------------------------------------ combine, Eq. (12)
@@ -479,19 +518,54 @@ hipError_t launch_conv_silu(int dtype, const void *xz, int64_t ld_xz, const floa
   return hipGetLastError();
 }
 
+int scan_chunks(int64_t B, int64_t L, int d_inner) {
+  // chunk only when there are fewer workgroups than CUs (256): the state-only pass costs about as
+  // much as the better occupancy of the full pass gains once every SIMD has a wavefront; chunks are whole tiles and at least 256 steps long
+  const int64_t blocks = B * (d_inner / kScanCh);
+  int64_t nc = ceil_div(256, blocks > 0 ? blocks : 1);
+  const int64_t by_len = L / 256;
+  if (nc > by_len) nc = by_len;
+  if (nc > 8) nc = 8;
+  if (nc < 1) nc = 1;
+  return static_cast<int>(nc);
+}
+
+size_t scan_chunk_state_bytes(int64_t B, int64_t L, int d_inner) {
+  const int nc = scan_chunks(B, L, d_inner);
+  return static_cast<size_t>(B) * (nc > 1 ? nc - 1 : 0) * d_inner * 16 * sizeof(float);
+}
+
+template <typename T>
+static hipError_t scan_dispatch(const T *u, const T *dt, const float *bc, const T *z, int64_t ld_z,
+                                const float *A_log, const float *D, const float *h_in, float *h_out, T *g,
+                                int64_t B, int64_t L, int d_inner, float *chunk_q, float *chunk_p,
+                                hipStream_t s) {
+  const int nc_max = scan_chunks(B, L, d_inner);
+  const int64_t chunk_len = ceil_div(ceil_div(L, nc_max), kScanTile) * kScanTile;
+  const int nc = static_cast<int>(ceil_div(L, chunk_len));      // no empty chunk after rounding
+  const unsigned gx = static_cast<unsigned>(d_inner / kScanCh), gy = static_cast<unsigned>(B);
+  if (nc > 1) {
+    hipLaunchKernelGGL((scan_kernel<T, true>), dim3(gx, gy, nc - 1), dim3(256), 0, s, u, dt, bc,
+                       static_cast<const T *>(nullptr), ld_z, A_log, D, static_cast<const float *>(nullptr),
+                       static_cast<float *>(nullptr), static_cast<T *>(nullptr), L, d_inner, chunk_len, nc,
+                       chunk_q, chunk_p);
+  }
+  hipLaunchKernelGGL((scan_kernel<T, false>), dim3(gx, gy, nc), dim3(256), 0, s, u, dt, bc, z, ld_z, A_log,
+                     D, h_in, h_out, g, L, d_inner, chunk_len, nc, chunk_q, chunk_p);
+  return hipGetLastError();
+}
+
 hipError_t launch_scan_gate(int dtype, const void *u, const void *dt, const float *bc, const void *z,
                             int64_t ld_z, const float *A_log, const float *D, const float *h_in,
-                            float *h_out, void *g, int64_t B, int64_t L, int d_inner, hipStream_t s) {
-  const dim3 grid(static_cast<unsigned>(d_inner / kScanCh), static_cast<unsigned>(B));
+                            float *h_out, void *g, int64_t B, int64_t L, int d_inner, float *chunk_q,
+                            float *chunk_p, hipStream_t s) {
   if (dtype == ROM_DTYPE_BF16)
-    hipLaunchKernelGGL(scan_gate_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(u),
-                       static_cast<const bf16_t *>(dt), bc, static_cast<const bf16_t *>(z), ld_z, A_log,
-                       D, h_in, h_out, static_cast<bf16_t *>(g), L, d_inner);
-  else
-    hipLaunchKernelGGL(scan_gate_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(u),
-                       static_cast<const float *>(dt), bc, static_cast<const float *>(z), ld_z, A_log, D,
-                       h_in, h_out, static_cast<float *>(g), L, d_inner);
-  return hipGetLastError();
+    return scan_dispatch<bf16_t>(static_cast<const bf16_t *>(u), static_cast<const bf16_t *>(dt), bc,
+                                 static_cast<const bf16_t *>(z), ld_z, A_log, D, h_in, h_out,
+                                 static_cast<bf16_t *>(g), B, L, d_inner, chunk_q, chunk_p, s);
+  return scan_dispatch<float>(static_cast<const float *>(u), static_cast<const float *>(dt), bc,
+                              static_cast<const float *>(z), ld_z, A_log, D, h_in, h_out,
+                              static_cast<float *>(g), B, L, d_inner, chunk_q, chunk_p, s);
 }
 
 hipError_t launch_combine(int dtype, const void *op, const int32_t *inv_perm, const float *gate,
