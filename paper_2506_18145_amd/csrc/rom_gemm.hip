@@ -494,13 +494,20 @@ hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s) {
   }
   if (a.c_is_f32) {
     if (a.N <= 192) {
+      // one column tile: the grid is the number of row tiles, so use 64-row tiles (two waves)
+      // when 128-row tiles would leave CUs without work
+      const bool small_rows = a.M / 128 + a.n_groups < 200;
       switch ((a.N + 31) / 32) {
-        case 1: return launch_mfma<128, 32, 4, 1, kEpiPlainF32>(a, s);
-        case 2: return launch_mfma<128, 64, 4, 1, kEpiPlainF32>(a, s);
-        case 3: return launch_mfma<128, 96, 4, 1, kEpiPlainF32>(a, s);
-        case 4: return launch_mfma<128, 128, 4, 1, kEpiPlainF32>(a, s);
-        case 5: return launch_mfma<128, 160, 4, 1, kEpiPlainF32>(a, s);
-        default: return launch_mfma<128, 192, 4, 1, kEpiPlainF32>(a, s);
+#define ROM_SKINNY(NN)                                                               \
+  return small_rows ? launch_mfma<64, NN, 2, 1, kEpiPlainF32>(a, s)                  \
+                    : launch_mfma<128, NN, 4, 1, kEpiPlainF32>(a, s)
+        case 1: ROM_SKINNY(32);
+        case 2: ROM_SKINNY(64);
+        case 3: ROM_SKINNY(96);
+        case 4: ROM_SKINNY(128);
+        case 5: ROM_SKINNY(160);
+        default: ROM_SKINNY(192);
+#undef ROM_SKINNY
       }
     }
     return launch_mfma_tiles<kEpiPlainF32>(a, s);

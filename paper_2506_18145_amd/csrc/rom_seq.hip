@@ -183,15 +183,17 @@ constexpr int kDppHalfMirror = 0x141;   // lane i <-> 7 - i inside each 8
 constexpr int kDppRowMirror = 0x140;    // lane i <-> 15 - i inside each 16
 constexpr int kDppRowBcast0 = 0x150;    // row_newbcast:0 (+j for lane j of the row)
 
-// elements per step row of the dt/u/z/g tiles (16 channels + padding that keeps rows 16-byte aligned)
-template <typename T> struct ScanPitch { static constexpr int v = kScanCh + 16 / sizeof(T); };
+// floats per step row of the dt/u/z/g tiles (16 channels + padding that keeps rows 16-byte aligned
+// and spreads the 16 steps a row of lanes reads over the banks).  The tiles hold floats: converting
+// once when a tile is parked is cheaper than converting in the issue-bound inner loop.
+constexpr int kChPitch = kScanCh + 4;
 
-template <typename T> struct __attribute__((aligned(16))) ScanSmem {
-  T dt[2][kScanTile][ScanPitch<T>::v];
-  T u[2][kScanTile][ScanPitch<T>::v];
-  T z[2][kScanTile][ScanPitch<T>::v];
+struct __attribute__((aligned(16))) ScanSmem {
+  float dt[2][kScanTile][kChPitch];
+  float u[2][kScanTile][kChPitch];
+  float z[2][kScanTile][kChPitch];
   float bc[2][32][kBcPitch];            // [buffer][B_0..B_15, C_0..C_15][step]
-  T g[2][kScanTile][ScanPitch<T>::v];
+  float g[2][kScanTile][kChPitch];
 };
 
 template <int J> struct StepSeq {
@@ -251,17 +253,33 @@ __device__ __forceinline__ float row_sum16(float v) {
 
 // N consecutive elements of T held in registers
 template <typename T, int N> struct Pack;
+__device__ __forceinline__ float bf16_word_get(unsigned int w, int odd) {
+  return __uint_as_float(odd ? (w & 0xFFFF0000u) : (w << 16));
+}
 template <> struct Pack<bf16_t, 8> {
   uint4 raw;
   __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const uint4 *>(p); }
-  __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<uint4 *>(p) = raw; }
   __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
+  __device__ __forceinline__ void park(float *p) const {      // as floats, 16-byte aligned
+    *reinterpret_cast<float4 *>(p) = make_float4(bf16_word_get(raw.x, 0), bf16_word_get(raw.x, 1),
+                                                 bf16_word_get(raw.y, 0), bf16_word_get(raw.y, 1));
+    *reinterpret_cast<float4 *>(p + 4) = make_float4(bf16_word_get(raw.z, 0), bf16_word_get(raw.z, 1),
+                                                     bf16_word_get(raw.w, 0), bf16_word_get(raw.w, 1));
+  }
 };
 template <> struct Pack<bf16_t, 4> {
   uint2 raw;
   __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const uint2 *>(p); }
-  __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<uint2 *>(p) = raw; }
   __device__ __forceinline__ void zero() { raw = make_uint2(0, 0); }
+  __device__ __forceinline__ void park(float *p) const {
+    *reinterpret_cast<float4 *>(p) = make_float4(bf16_word_get(raw.x, 0), bf16_word_get(raw.x, 1),
+                                                 bf16_word_get(raw.y, 0), bf16_word_get(raw.y, 1));
+  }
+  __device__ __forceinline__ void from_floats(const float4 &v) {
+    raw.x = pack_bf16x2(v.x, v.y);
+    raw.y = pack_bf16x2(v.z, v.w);
+  }
+  __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<uint2 *>(p) = raw; }
 };
 template <> struct Pack<float, 8> {
   float4 lo, hi;
@@ -269,17 +287,19 @@ template <> struct Pack<float, 8> {
     lo = *reinterpret_cast<const float4 *>(p);
     hi = *reinterpret_cast<const float4 *>(p + 4);
   }
-  __device__ __forceinline__ void store(float *p) const {
+  __device__ __forceinline__ void zero() { lo = make_float4(0.f, 0.f, 0.f, 0.f); hi = lo; }
+  __device__ __forceinline__ void park(float *p) const {
     *reinterpret_cast<float4 *>(p) = lo;
     *reinterpret_cast<float4 *>(p + 4) = hi;
   }
-  __device__ __forceinline__ void zero() { lo = make_float4(0.f, 0.f, 0.f, 0.f); hi = lo; }
 };
 template <> struct Pack<float, 4> {
   float4 raw;
   __device__ __forceinline__ void load(const float *p) { raw = *reinterpret_cast<const float4 *>(p); }
-  __device__ __forceinline__ void store(float *p) const { *reinterpret_cast<float4 *>(p) = raw; }
   __device__ __forceinline__ void zero() { raw = make_float4(0.f, 0.f, 0.f, 0.f); }
+  __device__ __forceinline__ void park(float *p) const { *reinterpret_cast<float4 *>(p) = raw; }
+  __device__ __forceinline__ void from_floats(const float4 &v) { raw = v; }
+  __device__ __forceinline__ void store(float *p) const { *reinterpret_cast<float4 *>(p) = raw; }
 };
 
 // One thread's share of a tile: 8 channels of one step of dt (threads 0..127) or u (128..255),
@@ -315,11 +335,11 @@ __device__ __forceinline__ void scan_fetch(ScanStage<T> &r, const T *dt_b, const
 }
 
 template <typename T, bool kStateOnly>
-__device__ __forceinline__ void scan_park(ScanSmem<T> &sm, int buf, const ScanStage<T> &r, int tid) {
-  r.du.store((tid < 128 ? &sm.dt[buf][0][0] : &sm.u[buf][0][0]) + ((tid & 127) >> 1) * ScanPitch<T>::v +
-             (tid & 1) * 8);
+__device__ __forceinline__ void scan_park(ScanSmem &sm, int buf, const ScanStage<T> &r, int tid) {
+  r.du.park((tid < 128 ? &sm.dt[buf][0][0] : &sm.u[buf][0][0]) + ((tid & 127) >> 1) * kChPitch +
+            (tid & 1) * 8);
   const int row = tid >> 2, part = tid & 3;
-  if (!kStateOnly) r.z.store(&sm.z[buf][row][part * 4]);
+  if (!kStateOnly) r.z.park(&sm.z[buf][row][part * 4]);
   if (!kStateOnly || part < 2) {
     const int col = part * 8;
     sm.bc[buf][col + 0][row] = r.bc0.x; sm.bc[buf][col + 1][row] = r.bc0.y;
@@ -338,7 +358,7 @@ __global__ __launch_bounds__(256) void scan_kernel(
     const float *__restrict__ D, const float *__restrict__ h_in, float *__restrict__ h_out,
     T *__restrict__ g, int64_t L, int d_inner, int64_t chunk_len, int n_chunks,
     float *__restrict__ chunk_q, float *__restrict__ chunk_p) {
-  __shared__ ScanSmem<T> sm;
+  __shared__ ScanSmem sm;
   const int tid = threadIdx.x;
   const int n = tid & 15;            // state index = lane inside the DPP row
   const int cl = tid >> 4;           // channel inside the block
@@ -394,8 +414,8 @@ __global__ __launch_bounds__(256) void scan_kernel(
 #pragma unroll
     for (int gi = 0; gi < kScanGroups; ++gi) {
       const int s0 = gi * 16;
-      const float dt_r = to_f32(sm.dt[buf][s0 + n][cl]);
-      const float u_r = to_f32(sm.u[buf][s0 + n][cl]);
+      const float dt_r = sm.dt[buf][s0 + n][cl];
+      const float u_r = sm.u[buf][s0 + n][cl];
       const float dtu_r = dt_r * u_r;
       float bv[16], hs[16];
 #pragma unroll
@@ -413,9 +433,9 @@ __global__ __launch_bounds__(256) void scan_kernel(
           const float4 c4 = *reinterpret_cast<const float4 *>(&sm.bc[buf][16 + n][s0 + j]);
           cv[j] = c4.x; cv[j + 1] = c4.y; cv[j + 2] = c4.z; cv[j + 3] = c4.w;
         }
-        const float z_r = to_f32(sm.z[buf][s0 + n][cl]);
+        const float z_r = sm.z[buf][s0 + n][cl];
         const float y = transpose_reduce16(hs, cv, n) + d_skip * u_r;
-        sm.g[buf][s0 + n][cl] = from_f32<T>(y * silu_f32(z_r));
+        sm.g[buf][s0 + n][cl] = y * silu_f32(z_r);
       }
     }
     if (has_next) scan_park<T, kStateOnly>(sm, buf ^ 1, st, tid);
@@ -425,7 +445,7 @@ __global__ __launch_bounds__(256) void scan_kernel(
       const int64_t t = t0 + r;
       if (t < t_end) {
         Pack<T, 4> pk;
-        pk.load(&sm.g[buf][r][q]);
+        pk.from_floats(*reinterpret_cast<const float4 *>(&sm.g[buf][r][q]));
         pk.store(g_b + t * d_inner + q);
       }
     }
