@@ -102,6 +102,24 @@ constexpr int kRowChunks = kBK / 8;
 // pairs; (r & 7) ^ ((r >> 3) & 1) does that and stays conflict-free on 8-row groups as well.
 __device__ __forceinline__ int lds_swizzle(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 
+// Scheduling hints for one 16-wide step: after MFMA number I, one LDS fragment read (while there
+// are any) and this MFMA's share of the LDS writes that park the next slab.
+template <int MMA, int READS, int PARKS, bool WITH_PARKS, int I> struct InterleaveHints {
+  __device__ static __forceinline__ void run() {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // one MFMA
+    if constexpr (I < READS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one DS read
+    if constexpr (WITH_PARKS) {
+      constexpr int lo = I * PARKS / MMA, hi = (I + 1) * PARKS / MMA;
+      if constexpr (hi > lo) __builtin_amdgcn_sched_group_barrier(0x200, hi - lo, 0);   // DS writes
+    }
+    InterleaveHints<MMA, READS, PARKS, WITH_PARKS, I + 1>::run();
+  }
+};
+template <int MMA, int READS, int PARKS, bool WITH_PARKS>
+struct InterleaveHints<MMA, READS, PARKS, WITH_PARKS, MMA> {
+  __device__ static __forceinline__ void run() {}
+};
+
 // PA / PB: how many K slabs ahead the global loads of the activation / weight operand run
 // (1 or 2; each extra slab costs one more register set for that operand).
 // KTAIL: K is not a multiple of the slab, the last slab is zero-filled past K.
@@ -244,15 +262,10 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
       for (int j = 0; j < TN; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
   };
-  // ask the scheduler to put the next step's LDS fragment reads between the first MFMAs of this
-  // step (one read per MFMA), so that every fragment has most of a step to arrive
-  auto interleave_reads = [&]() __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < TM + TN; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one DS read
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+  // ask the scheduler to put the next step's LDS fragment reads (and, in one step per slab, the
+  // LDS writes that park the next slab) between the MFMAs of this step, one per MFMA
+  auto interleave = [&](auto with_parks) __attribute__((always_inline)) {
+    InterleaveHints<TM * TN, TM + TN, A_CH + B_CH, decltype(with_parks)::value, 0>::run();
   };
 
   load_a(0, Set0{});
@@ -277,19 +290,25 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
     const int ka = (kt + PA) * kBK, kb = (kt + PB) * kBK;
     load_a(ka < k_end ? ka : k_end, LoadA{});
     load_b(kb < k_end ? kb : k_end, LoadB{});
+    // The next slab (loaded while the previous one was multiplied) is parked in the middle of
+    // this slab, its LDS writes spread between MFMAs, instead of in a burst before the barrier.
+    constexpr int kParkAt = 3;       // 0..2: interleaved with that 16-wide step; 3: after the third step.
+                                     // Measured: any earlier than 3 stalls on the loads still in flight.
     load_frags(PAR, 1, fa[1], fb[1]);
+    if (kParkAt == 0) { park_a(PAR ^ 1, ParkA{}); park_b(PAR ^ 1, ParkB{}); }
     mma(fa[0], fb[0]);
-    interleave_reads();
+    interleave(std::bool_constant<kParkAt == 0>{});
     load_frags(PAR, 2, fa[0], fb[0]);
+    if (kParkAt == 1) { park_a(PAR ^ 1, ParkA{}); park_b(PAR ^ 1, ParkB{}); }
     mma(fa[1], fb[1]);
-    interleave_reads();
+    interleave(std::bool_constant<kParkAt == 1>{});
     load_frags(PAR, 3, fa[1], fb[1]);
+    if (kParkAt == 2) { park_a(PAR ^ 1, ParkA{}); park_b(PAR ^ 1, ParkB{}); }
     mma(fa[0], fb[0]);
-    interleave_reads();
-    // every fragment of this slab is in registers: park the next slab, then overlap the fetch
+    interleave(std::bool_constant<kParkAt == 2>{});
+    if (kParkAt == 3) { park_a(PAR ^ 1, ParkA{}); park_b(PAR ^ 1, ParkB{}); }
+    // every fragment of this slab is in registers and the next slab is parked: overlap the fetch
     // of its first fragments with the last 16-wide step of this one
-    park_a(PAR ^ 1, ParkA{});
-    park_b(PAR ^ 1, ParkB{});
     __syncthreads();
     load_frags(PAR ^ 1, 0, fa[0], fb[0]);
     mma(fa[1], fb[1]);

@@ -459,6 +459,31 @@ __global__ __launch_bounds__(256) void scan_kernel(
   }
 }
 
+// ------------------------------------------------------------------ single-step scan (L == 1)
+// One recurrence update per (sequence, channel, state): bound by reading and writing the fp32
+// state.  Lane = (channel, state) again, so a row of 16 lanes reduces C.h with four DPP adds.
+template <typename T>
+__global__ __launch_bounds__(256) void scan_step_kernel(
+    const T *__restrict__ u, const T *__restrict__ dt, const float *__restrict__ bc,
+    const T *__restrict__ z, int64_t ld_z, const float *__restrict__ A_log,
+    const float *__restrict__ D, const float *__restrict__ h_in, float *__restrict__ h_out,
+    T *__restrict__ g, int64_t n_seq, int d_inner) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int n = threadIdx.x & 15;
+  const int64_t bc_idx = idx >> 4;                 // (sequence, channel)
+  if (bc_idx >= n_seq * d_inner) return;           // whole rows of 16 lanes leave together
+  const int64_t b = bc_idx / d_inner;
+  const int ch = static_cast<int>(bc_idx % d_inner);
+  const float a2 = -__expf(A_log[static_cast<int64_t>(ch) * 16 + n]) * 1.44269504088896341f;
+  const float dt_r = to_f32(dt[bc_idx]);
+  const float u_r = to_f32(u[bc_idx]);
+  const float h_prev = h_in ? h_in[idx] : 0.0f;
+  const float h = fmaf(fast_exp2(dt_r * a2), h_prev, dt_r * u_r * bc[b * 32 + n]);
+  if (h_out) h_out[idx] = h;
+  const float y = row_sum16(h * bc[b * 32 + 16 + n]) + D[ch] * u_r;
+  if (n == 0) g[bc_idx] = from_f32<T>(y * silu_f32(to_f32(z[b * ld_z + ch])));
+}
+
 // ------------------------------------------------------------------ combine, Eq. (12)
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(const T *__restrict__ op,
@@ -560,6 +585,12 @@ static hipError_t scan_dispatch(const T *u, const T *dt, const float *bc, const 
                                 const float *A_log, const float *D, const float *h_in, float *h_out, T *g,
                                 int64_t B, int64_t L, int d_inner, float *chunk_q, float *chunk_p,
                                 hipStream_t s) {
+  if (L == 1) {
+    const int64_t lanes = B * d_inner * 16;
+    hipLaunchKernelGGL((scan_step_kernel<T>), dim3(static_cast<unsigned>(ceil_div(lanes, 256))), dim3(256),
+                       0, s, u, dt, bc, z, ld_z, A_log, D, h_in, h_out, g, B, d_inner);
+    return hipGetLastError();
+  }
   const int nc_max = scan_chunks(B, L, d_inner);
   const int64_t chunk_len = ceil_div(ceil_div(L, nc_max), kScanTile) * kScanTile;
   const int nc = static_cast<int>(ceil_div(L, chunk_len));      // no empty chunk after rounding
