@@ -67,7 +67,7 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   p.xz = take(N * 2 * De * b);
   p.xz_sorted = multi ? take(S * 2 * De * b) : kNone;
   p.u = take(N * De * b);
-  p.xdbl = take((routed_xdt ? S : N) * (R + 32) * 4);
+  p.xdbl = take((routed_xdt ? S : N) * (R + 32) * 4 * xproj_k_splits(routed_xdt ? S : N, d->d_inner));
   p.dt_low = take(N * R * b);
   p.bc = take(N * 32 * 4);
   p.dt = take(N * De * b);
@@ -192,6 +192,13 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   ga.A = at(p.u); ga.lda = De; ga.a_span = N * De;
   ga.W = w->w_x; ga.N = R + 32; ga.K = De;
   ga.C = at(p.xdbl); ga.ldc = R + 32; ga.c_is_f32 = 1;
+  const int64_t x_rows = routed_xdt ? S : N;
+  ga.k_splits = xproj_k_splits(x_rows, De);
+  {   // the slice length is rounded up to whole 64-wide slabs: use the slice count that results
+    const int64_t per = ceil_div(ceil_div(De, ga.k_splits), 64) * 64;
+    ga.k_splits = static_cast<int>(ceil_div(De, per));
+  }
+  ga.c_split_stride = x_rows * (R + 32);
   if (routed_xdt) {
     ga.a_rows = tok_of_pos; ga.offsets = offsets; ga.n_groups = E; ga.M = S;
     ga.c_rows = multi ? nullptr : tok_of_pos;
@@ -199,7 +206,7 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
     ga.n_groups = 1; ga.M = N;
   }
   ROM_TRY(launch_grouped_gemm(ga, s));
-  ROM_TRY(launch_split_xdbl(d->dtype, static_cast<const float *>(at(p.xdbl)),
+  ROM_TRY(launch_split_xdbl(d->dtype, static_cast<const float *>(at(p.xdbl)), ga.k_splits, ga.c_split_stride,
                             (routed_xdt && multi) ? inv_perm : nullptr, K, N, R, at(p.dt_low),
                             static_cast<float *>(at(p.bc)), s));
   mark.done(ROM_STAGE_X_PROJ);

@@ -88,7 +88,7 @@ __device__ __forceinline__ void store_out(const GemmArgs &a, int64_t crow, int c
   if (a.softplus) v = softplus_f32(v);
   if (a.row_scale) v *= a.row_scale[crow];
   if (a.c_is_f32 || a.dtype == ROM_DTYPE_F32)
-    static_cast<float *>(a.C)[crow * a.ldc + col] = v;
+    static_cast<float *>(a.C)[blockIdx.y * a.c_split_stride + crow * a.ldc + col] = v;
   else
     static_cast<bf16_t *>(a.C)[crow * a.ldc + col] = f32_to_bf16(v);
 }
@@ -163,8 +163,11 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
     const int n = (tc.n0 + r < a.N) ? tc.n0 + r : a.N - 1;
     b_src[i] = static_cast<uint32_t>(n) * static_cast<uint32_t>(a.K);
   }
-  const int k_chunk = (tid % kRowChunks) * 8;
-  const int k_last = a.K - 8;
+  // split-K: grid.y slices of k_per_split inner-dimension elements, each with its own fp32 output
+  const int k_begin = blockIdx.y * a.k_per_split;
+  const int k_len = (a.K - k_begin < a.k_per_split) ? a.K - k_begin : a.k_per_split;
+  const int k_chunk = k_begin + (tid % kRowChunks) * 8;
+  const int k_last = k_begin + k_len - 8;
 
   // Register sets for slabs in flight: with depth 2 the global loads of slab kt+2 are issued while
   // slab kt is multiplied, so they have two slab times to land before they are parked in LDS
@@ -179,7 +182,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (!KTAIL || k0 + kBK <= a.K) v = *reinterpret_cast<const uint4 *>(Ap + a_src[i] + k);
+      if (!KTAIL || k0 + kBK <= k_len) v = *reinterpret_cast<const uint4 *>(Ap + a_src[i] + k);
       else if (k_ok) v = *reinterpret_cast<const uint4 *>(Ap + a_src[i] + k);
       if constexpr (S == 0) ra0[i] = v; else ra1[i] = v;
     }
@@ -191,7 +194,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) {
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (!KTAIL || k0 + kBK <= a.K) v = *reinterpret_cast<const uint4 *>(Wp + b_src[i] + k);
+      if (!KTAIL || k0 + kBK <= k_len) v = *reinterpret_cast<const uint4 *>(Wp + b_src[i] + k);
       else if (k_ok) v = *reinterpret_cast<const uint4 *>(Wp + b_src[i] + k);
       if constexpr (S == 0) rb0[i] = v; else rb1[i] = v;
     }
@@ -227,7 +230,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  const int KT = (a.K + kBK - 1) / kBK;
+  const int KT = (k_len + kBK - 1) / kBK;
   const int frag_row = lane & 31, frag_half = lane >> 5;
   // LDS chunk index of this lane's fragment for 16-wide K step kk: row * 8 + ((2 kk + half) ^ swizzle(row));
   // the wave / tile row offsets are multiples of 32, so the swizzle term depends on the lane only.
@@ -336,7 +339,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
         for (int q = 0; q < 4; ++q) {
           const int col = tc.n0 + wn * WTN + j * 32 + q * 8 + frag_half * 4;
           if (row_ok && col < a.N)
-            *reinterpret_cast<float4 *>(static_cast<float *>(a.C) + crow * a.ldc + col) =
+            *reinterpret_cast<float4 *>(static_cast<float *>(a.C) + blockIdx.y * a.c_split_stride +
+                                        crow * a.ldc + col) =
                 make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
         }
       }
@@ -416,12 +420,14 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const GemmArgs a) {
   const int64_t a_off = (pa < tc.row_end) ? static_cast<int64_t>(a.a_rows ? a.a_rows[pa] : pa) * a.lda : -1;
   const int64_t b_off = (tc.n0 + s_r < a.N) ? static_cast<int64_t>(tc.n0 + s_r) * a.K : -1;
   float acc[4][4] = {};
-  for (int k0 = 0; k0 < a.K; k0 += kSK) {
+  const int k_begin = blockIdx.y * a.k_per_split;
+  const int k_stop = (a.K - k_begin < a.k_per_split) ? a.K : k_begin + a.k_per_split;
+  for (int k0 = k_begin; k0 < k_stop; k0 += kSK) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int k = k0 + s_k + i;
-      As[s_k + i][s_r] = (a_off >= 0 && k < a.K) ? to_f32(Ap[a_off + k]) : 0.0f;
-      Bs[s_k + i][s_r] = (b_off >= 0 && k < a.K) ? to_f32(Wp[b_off + k]) : 0.0f;
+      As[s_k + i][s_r] = (a_off >= 0 && k < k_stop) ? to_f32(Ap[a_off + k]) : 0.0f;
+      Bs[s_k + i][s_r] = (b_off >= 0 && k < k_stop) ? to_f32(Wp[b_off + k]) : 0.0f;
     }
     __syncthreads();
 #pragma unroll
@@ -471,13 +477,13 @@ hipError_t launch_mfma_k(const GemmArgs &a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_bf16_mfma_kernel<BM, BN, WM, WN, EPI, KTAIL>), dim3(grid_tiles(a, BM, BN)),
-                     dim3(WM * WN * 64), kSmem, s, a);
+  hipLaunchKernelGGL((gemm_bf16_mfma_kernel<BM, BN, WM, WN, EPI, KTAIL>),
+                     dim3(grid_tiles(a, BM, BN), a.k_splits), dim3(WM * WN * 64), kSmem, s, a);
   return hipGetLastError();
 }
 template <int BM, int BN, int WM, int WN, int EPI>
 hipError_t launch_mfma(const GemmArgs &a, hipStream_t s) {
-  if (a.K % kBK == 0) return launch_mfma_k<BM, BN, WM, WN, EPI, false>(a, s);
+  if (a.K % kBK == 0 && a.k_per_split % kBK == 0) return launch_mfma_k<BM, BN, WM, WN, EPI, false>(a, s);
   return launch_mfma_k<BM, BN, WM, WN, EPI, true>(a, s);
 }
 
@@ -493,8 +499,12 @@ hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s) {
-  if (a.M <= 0) return hipSuccess;
+hipError_t launch_grouped_gemm(const GemmArgs &args, hipStream_t s) {
+  if (args.M <= 0) return hipSuccess;
+  GemmArgs a = args;
+  if (a.k_splits < 1 || !a.c_is_f32 || a.bias || a.row_scale) a.k_splits = 1;   // partial sums need a plain fp32 output
+  a.k_per_split = static_cast<int>(ceil_div(ceil_div(a.K, a.k_splits), 64) * 64);
+  a.k_splits = static_cast<int>(ceil_div(a.K, a.k_per_split));
   const int out_align = a.c_is_f32 ? 4 : 8;      // elements per output store
   const bool mfma_ok = a.dtype == ROM_DTYPE_BF16 && a.K % 8 == 0 && a.lda % 8 == 0 &&
                        a.N % out_align == 0 && a.ldc % out_align == 0 && (reinterpret_cast<uintptr_t>(a.A) % 16 == 0) &&
@@ -504,7 +514,7 @@ hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s) {
                        !(a.bias && !a.softplus) && !(a.softplus && !a.bias) &&
                        !(a.row_scale && (a.bias || a.c_is_f32)) && !(a.bias && a.c_is_f32);
   if (!mfma_ok) {
-    const dim3 grid(grid_tiles(a, kSB, kSB));
+    const dim3 grid(grid_tiles(a, kSB, kSB), a.k_splits);
     if (a.dtype == ROM_DTYPE_BF16)
       hipLaunchKernelGGL(gemm_simple_kernel<bf16_t>, grid, dim3(256), 0, s, a);
     else

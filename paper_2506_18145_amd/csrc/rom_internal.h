@@ -69,6 +69,10 @@ struct GemmArgs {
   const float *bias;         // [N] or NULL: added before softplus
   int softplus;              // apply softplus after bias
   const float *row_scale;    // indexed by c_row (NULL = 1): multiplies the row
+  int k_splits;              // > 1: slice the inner dimension; slice s writes its partial sums (fp32, plain
+                             // epilogue only) to C + s * c_split_stride; the consumer adds the slices up
+  int64_t c_split_stride;    // elements between the outputs of consecutive slices
+  int k_per_split;           // filled in by launch_grouped_gemm
 };
 hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s);
 
@@ -78,8 +82,11 @@ hipError_t launch_slot_sum(int src_is_f32, int dst_is_f32, const void *src, int6
                            int64_t ld_dst, const int32_t *inv_perm, int64_t n_tokens, int top_k,
                            int n_cols, const float *bias, int softplus, hipStream_t s);
 // xdbl (f32 [*, R + 32], token order or sorted) -> dt_low (T [N, R]) and bc (f32 [N, 32])
-hipError_t launch_split_xdbl(int dtype, const float *xdbl, const int32_t *inv_perm, int top_k,
-                             int64_t n_tokens, int dt_rank, void *dt_low, float *bc, hipStream_t s);
+hipError_t launch_split_xdbl(int dtype, const float *xdbl, int n_slices, int64_t slice_stride,
+                             const int32_t *inv_perm, int top_k, int64_t n_tokens, int dt_rank,
+                             void *dt_low, float *bc, hipStream_t s);
+// number of inner-dimension slices the x projection is cut into (small batches only)
+int xproj_k_splits(int64_t rows, int d_inner);
 hipError_t launch_conv_silu(int dtype, const void *xz, int64_t ld_xz, const float *conv_w,
                             const float *conv_b, const float *state_in, float *state_out, void *u,
                             int64_t B, int64_t L, int d_inner, hipStream_t s);

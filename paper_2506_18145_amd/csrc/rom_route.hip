@@ -196,6 +196,64 @@ __global__ __launch_bounds__(kSortBlock) void scatter_kernel(
   tok_of_pos[pos] = static_cast<int32_t>(s / top_k);
 }
 
+// Whole grouping in one workgroup for small slot counts (decode steps): three passes over the
+// slots in rounds of 256, counts and running bases in LDS.
+__global__ __launch_bounds__(kSortBlock) void permutation_small_kernel(
+    const int32_t *__restrict__ expert_idx, int n_slots, int n_experts, int top_k,
+    int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
+    int32_t *__restrict__ inv_perm, int32_t *__restrict__ tok_of_pos) {
+  __shared__ int cnt[kSortWaves][64];
+  __shared__ int base[64];          // running position of every expert
+  __shared__ int total[64];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  if (threadIdx.x < 64) total[threadIdx.x] = 0;
+  __syncthreads();
+  for (int s0 = 0; s0 < n_slots; s0 += kSortBlock) {      // histogram
+    const int s = s0 + threadIdx.x;
+    match_expert(s < n_slots ? expert_idx[s] : -1, n_experts, lane, cnt[wave]);
+    __syncthreads();
+    if (threadIdx.x < n_experts) {
+      int t = 0;
+#pragma unroll
+      for (int w = 0; w < kSortWaves; ++w) t += cnt[w][threadIdx.x];
+      total[threadIdx.x] += t;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int e = 0; e < n_experts; ++e) {
+      offsets[e] = run;
+      base[e] = run;
+      counts[e] = total[e];
+      run += total[e];
+    }
+    offsets[n_experts] = run;
+  }
+  __syncthreads();
+  for (int s0 = 0; s0 < n_slots; s0 += kSortBlock) {      // stable scatter
+    const int s = s0 + threadIdx.x;
+    const int key = s < n_slots ? expert_idx[s] : -1;
+    const unsigned long long same = match_expert(key, n_experts, lane, cnt[wave]);
+    __syncthreads();
+    if (s < n_slots) {
+      int pos = base[key] + __popcll(same & ((1ull << lane) - 1ull));
+      for (int w = 0; w < wave; ++w) pos += cnt[w][key];
+      inv_perm[s] = pos;
+      perm[pos] = s;
+      tok_of_pos[pos] = s / top_k;
+    }
+    __syncthreads();
+    if (threadIdx.x < n_experts) {
+      int t = 0;
+#pragma unroll
+      for (int w = 0; w < kSortWaves; ++w) t += cnt[w][threadIdx.x];
+      base[threadIdx.x] += t;
+    }
+    __syncthreads();
+  }
+}
+
 template <typename T>
 hipError_t route_dispatch(const void *x, const void *w_router, const float *b_router,
                           int64_t n_tokens, int d_model, int n_experts, int top_k, int gate_mode,
@@ -210,7 +268,10 @@ hipError_t route_dispatch(const void *x, const void *w_router, const float *b_ro
                        dim3(256), 0, s, xp, wp, b_router, n_tokens, d_model, n_experts, top_k,   \
                        gate_mode, expert_idx, gate, logits);                                     \
   } while (0)
-  if (n_experts <= 8) ROM_ROUTE_LAUNCH(8, 4);
+  // few tokens: one token per wavefront so that the launch still spreads over the chip
+  if (n_tokens <= 8192 && n_experts <= 8) ROM_ROUTE_LAUNCH(8, 1);
+  else if (n_tokens <= 8192 && n_experts <= 16) ROM_ROUTE_LAUNCH(16, 1);
+  else if (n_experts <= 8) ROM_ROUTE_LAUNCH(8, 4);
   else if (n_experts <= 16) ROM_ROUTE_LAUNCH(16, 2);
   else if (n_experts <= 32) ROM_ROUTE_LAUNCH(32, 1);
   else ROM_ROUTE_LAUNCH(64, 1);
@@ -235,6 +296,11 @@ hipError_t launch_route_topk(int dtype, const void *x, const void *w_router, con
 hipError_t launch_permutation(const int32_t *expert_idx, int64_t n_slots, int n_experts, int top_k,
                               int32_t *block_counts, int32_t *counts, int32_t *offsets,
                               int32_t *perm, int32_t *inv_perm, int32_t *tok_of_pos, hipStream_t s) {
+  if (n_slots <= 2048) {
+    hipLaunchKernelGGL(permutation_small_kernel, dim3(1), dim3(kSortBlock), 0, s, expert_idx,
+                       static_cast<int>(n_slots), n_experts, top_k, counts, offsets, perm, inv_perm, tok_of_pos);
+    return hipGetLastError();
+  }
   const int64_t blocks = route_blocks(n_slots);
   hipLaunchKernelGGL(hist_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kSortBlock), 0, s,
                      expert_idx, n_slots, n_experts, block_counts);

@@ -66,7 +66,8 @@ __global__ __launch_bounds__(256) void slot_sum_kernel(const TS *__restrict__ sr
 
 // xdbl rows (f32, R + 32 columns) -> dt_low (T) and bc (f32); sums the K slots when inv_perm is given
 template <typename T>
-__global__ __launch_bounds__(256) void split_xdbl_kernel(const float *__restrict__ xdbl,
+__global__ __launch_bounds__(256) void split_xdbl_kernel(const float *__restrict__ xdbl, int n_slices,
+                                                         int64_t slice_stride,
                                                          const int32_t *__restrict__ inv_perm,
                                                          int top_k, int64_t n_tokens, int dt_rank,
                                                          T *__restrict__ dt_low, float *__restrict__ bc) {
@@ -76,10 +77,13 @@ __global__ __launch_bounds__(256) void split_xdbl_kernel(const float *__restrict
   const int64_t n = idx / n_cols;
   const int c = static_cast<int>(idx % n_cols);
   float acc = 0.0f;
-  if (inv_perm) {
-    for (int k = 0; k < top_k; ++k) acc += xdbl[static_cast<int64_t>(inv_perm[n * top_k + k]) * n_cols + c];
-  } else {
-    acc = xdbl[n * n_cols + c];
+  for (int sl = 0; sl < n_slices; ++sl) {      // split-K partial sums, fixed order
+    const float *src = xdbl + sl * slice_stride;
+    if (inv_perm) {
+      for (int k = 0; k < top_k; ++k) acc += src[static_cast<int64_t>(inv_perm[n * top_k + k]) * n_cols + c];
+    } else {
+      acc += src[n * n_cols + c];
+    }
   }
   if (c < dt_rank) dt_low[n * dt_rank + c] = from_f32<T>(acc);
   else bc[n * 32 + (c - dt_rank)] = acc;
@@ -112,7 +116,22 @@ __global__ __launch_bounds__(256) void conv_silu_kernel(
     bias[i] = conv_b ? conv_b[c0 + i] : 0.0f;
   }
   const T *xrow = xz + b * L * ld_xz + c0;
-  // history: inputs at t0-3, t0-2, t0-1
+  // history: inputs at t0-3, t0-2, t0-1.  The carried state of the V channels of this thread is
+  // 3*V consecutive floats ([channel][3], oldest first): read with 16-byte loads.
+  float st[3 * V];
+  if (t0 < 3) {
+    if (state_in) {
+      const float4 *sp = reinterpret_cast<const float4 *>(state_in + (b * d_inner + c0) * 3);
+#pragma unroll
+      for (int i = 0; i < 3 * V / 4; ++i) {
+        const float4 v = sp[i];
+        st[4 * i] = v.x; st[4 * i + 1] = v.y; st[4 * i + 2] = v.z; st[4 * i + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 3 * V; ++i) st[i] = 0.0f;
+    }
+  }
 #pragma unroll
   for (int j = 0; j < 3; ++j) {
     const int64_t t = t0 - 3 + j;
@@ -123,8 +142,7 @@ __global__ __launch_bounds__(256) void conv_silu_kernel(
       for (int i = 0; i < V; ++i) h[j][i] = ch.get(i);
     } else {
 #pragma unroll
-      for (int i = 0; i < V; ++i)   // t = -3..-1 -> state slot 3 + t
-        h[j][i] = state_in ? state_in[(b * d_inner + c0 + i) * 3 + (3 + t)] : 0.0f;
+      for (int i = 0; i < V; ++i) h[j][i] = st[i * 3 + j];   // t0 == 0 here: t = -3..-1 -> slot j
     }
   }
   T *urow = u + b * L * d_inner + c0;
@@ -144,10 +162,14 @@ __global__ __launch_bounds__(256) void conv_silu_kernel(
     out.store(urow + t * d_inner);
   }
   if (state_out && t1 == L) {
+    float4 *sp = reinterpret_cast<float4 *>(state_out + (b * d_inner + c0) * 3);
+    float so[3 * V];
 #pragma unroll
-    for (int j = 0; j < 3; ++j)
+    for (int i = 0; i < V; ++i)
 #pragma unroll
-      for (int i = 0; i < V; ++i) state_out[(b * d_inner + c0 + i) * 3 + j] = h[j][i];
+      for (int j = 0; j < 3; ++j) so[i * 3 + j] = h[j][i];
+#pragma unroll
+    for (int i = 0; i < 3 * V / 4; ++i) sp[i] = make_float4(so[4 * i], so[4 * i + 1], so[4 * i + 2], so[4 * i + 3]);
   }
 }
 
@@ -461,7 +483,8 @@ __global__ __launch_bounds__(256) void scan_kernel(
 
 // ------------------------------------------------------------------ single-step scan (L == 1)
 // One recurrence update per (sequence, channel, state): bound by reading and writing the fp32
-// state.  Lane = (channel, state) again, so a row of 16 lanes reduces C.h with four DPP adds.
+// state.  A lane owns four consecutive states of one channel (one 16-byte load and store), four
+// lanes share a channel and reduce C.h with two DPP adds inside their quad.
 template <typename T>
 __global__ __launch_bounds__(256) void scan_step_kernel(
     const T *__restrict__ u, const T *__restrict__ dt, const float *__restrict__ bc,
@@ -469,19 +492,31 @@ __global__ __launch_bounds__(256) void scan_step_kernel(
     const float *__restrict__ D, const float *__restrict__ h_in, float *__restrict__ h_out,
     T *__restrict__ g, int64_t n_seq, int d_inner) {
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  const int n = threadIdx.x & 15;
-  const int64_t bc_idx = idx >> 4;                 // (sequence, channel)
-  if (bc_idx >= n_seq * d_inner) return;           // whole rows of 16 lanes leave together
+  const int q = threadIdx.x & 3;                   // which four states
+  const int64_t bc_idx = idx >> 2;                 // (sequence, channel)
+  if (bc_idx >= n_seq * d_inner) return;           // whole quads leave together
   const int64_t b = bc_idx / d_inner;
   const int ch = static_cast<int>(bc_idx % d_inner);
-  const float a2 = -__expf(A_log[static_cast<int64_t>(ch) * 16 + n]) * 1.44269504088896341f;
+  const float4 al = *reinterpret_cast<const float4 *>(A_log + static_cast<int64_t>(ch) * 16 + q * 4);
+  const float4 bv = *reinterpret_cast<const float4 *>(bc + b * 32 + q * 4);
+  const float4 cv = *reinterpret_cast<const float4 *>(bc + b * 32 + 16 + q * 4);
   const float dt_r = to_f32(dt[bc_idx]);
   const float u_r = to_f32(u[bc_idx]);
-  const float h_prev = h_in ? h_in[idx] : 0.0f;
-  const float h = fmaf(fast_exp2(dt_r * a2), h_prev, dt_r * u_r * bc[b * 32 + n]);
-  if (h_out) h_out[idx] = h;
-  const float y = row_sum16(h * bc[b * 32 + 16 + n]) + D[ch] * u_r;
-  if (n == 0) g[bc_idx] = from_f32<T>(y * silu_f32(to_f32(z[b * ld_z + ch])));
+  const float dtu = dt_r * u_r;
+  float4 h = h_in ? *reinterpret_cast<const float4 *>(h_in + idx * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+  const float k = -1.44269504088896341f * dt_r;
+  h.x = fmaf(fast_exp2(k * __expf(al.x)), h.x, dtu * bv.x);
+  h.y = fmaf(fast_exp2(k * __expf(al.y)), h.y, dtu * bv.y);
+  h.z = fmaf(fast_exp2(k * __expf(al.z)), h.z, dtu * bv.z);
+  h.w = fmaf(fast_exp2(k * __expf(al.w)), h.w, dtu * bv.w);
+  if (h_out) *reinterpret_cast<float4 *>(h_out + idx * 4) = h;
+  float part = h.x * cv.x + h.y * cv.y + h.z * cv.z + h.w * cv.w;
+  {
+#pragma clang fp contract(off)
+    part = dpp<kDppQuadXor1>(part) + part;
+    part = dpp<0x4E>(part) + part;                 // quad_perm [2,3,0,1]
+  }
+  if (q == 0) g[bc_idx] = from_f32<T>((part + D[ch] * u_r) * silu_f32(to_f32(z[b * ld_z + ch])));
 }
 
 // ------------------------------------------------------------------ combine, Eq. (12)
@@ -534,14 +569,24 @@ hipError_t launch_slot_sum(int src_is_f32, int dst_is_f32, const void *src, int6
   return hipGetLastError();
 }
 
-hipError_t launch_split_xdbl(int dtype, const float *xdbl, const int32_t *inv_perm, int top_k,
-                             int64_t n_tokens, int dt_rank, void *dt_low, float *bc, hipStream_t s) {
+int xproj_k_splits(int64_t rows, int d_inner) {
+  // few rows: the grid of row tiles cannot fill the chip, so cut the long inner dimension instead
+  if (rows > 4096 || d_inner < 1024) return 1;
+  const int by_len = d_inner / 512;
+  return by_len > 8 ? 8 : (by_len < 1 ? 1 : by_len);
+}
+
+hipError_t launch_split_xdbl(int dtype, const float *xdbl, int n_slices, int64_t slice_stride,
+                             const int32_t *inv_perm, int top_k, int64_t n_tokens, int dt_rank,
+                             void *dt_low, float *bc, hipStream_t s) {
   const dim3 grid = grid1d(n_tokens * (dt_rank + 32), 256);
   if (dtype == ROM_DTYPE_BF16)
-    hipLaunchKernelGGL(split_xdbl_kernel<bf16_t>, grid, dim3(256), 0, s, xdbl, inv_perm, top_k,
+    hipLaunchKernelGGL(split_xdbl_kernel<bf16_t>, grid, dim3(256), 0, s, xdbl, n_slices, slice_stride,
+                       inv_perm, top_k,
                        n_tokens, dt_rank, static_cast<bf16_t *>(dt_low), bc);
   else
-    hipLaunchKernelGGL(split_xdbl_kernel<float>, grid, dim3(256), 0, s, xdbl, inv_perm, top_k,
+    hipLaunchKernelGGL(split_xdbl_kernel<float>, grid, dim3(256), 0, s, xdbl, n_slices, slice_stride,
+                       inv_perm, top_k,
                        n_tokens, dt_rank, static_cast<float *>(dt_low), bc);
   return hipGetLastError();
 }
@@ -586,7 +631,7 @@ static hipError_t scan_dispatch(const T *u, const T *dt, const float *bc, const 
                                 int64_t B, int64_t L, int d_inner, float *chunk_q, float *chunk_p,
                                 hipStream_t s) {
   if (L == 1) {
-    const int64_t lanes = B * d_inner * 16;
+    const int64_t lanes = B * d_inner * 4;
     hipLaunchKernelGGL((scan_step_kernel<T>), dim3(static_cast<unsigned>(ceil_div(lanes, 256))), dim3(256),
                        0, s, u, dt, bc, z, ld_z, A_log, D, h_in, h_out, g, B, d_inner);
     return hipGetLastError();
