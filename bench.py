@@ -71,6 +71,36 @@ def cpu_baseline(cfg, sample_tokens):
                       f"{dt:.1f} s wall"}
 
 
+def decode_step_rate(n_steps=512):
+    """rom_step on the recurrent-decode workload (cfg4): 256 sequences, 512 consecutive steps,
+    states carried on the device.  Reported next to the headline number, not part of it."""
+    import torch
+    from paper_2506_18145_amd import RomLayer
+    from rom_synth import get_config, make_states, make_step_inputs, make_weights
+    cfg = get_config("cfg4")
+    layer = RomLayer(cfg, make_weights(cfg), device="cuda:0")
+    cs, ss = make_states(cfg)
+    cs, ss = layer.to_device(cs, typed=False), layer.to_device(ss, typed=False)
+    xs = layer.to_device(make_step_inputs(cfg, 64))
+    out = torch.empty_like(xs[0])
+    for i in range(16):
+        layer.step(xs[i], cs, ss, out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n_steps):
+        layer.step(xs[i % 64], cs, ss, out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    # algorithmic HBM bytes per step: every expert's weights once + fp32 state read and written
+    De, Dm, R, E = cfg.d_inner, cfg.d_model, cfg.dt_rank, cfg.n_experts
+    w_bytes = 2 * E * (2 * De * Dm + (R + 32) * De + De * R + Dm * De)
+    s_bytes = 2 * 4 * cfg.batch * De * (16 + 3)
+    return {"workload": "cfg4: 256 sequences x %d steps, d_model=2048, E=8, top-1, bf16" % n_steps,
+            "us_per_step": dt / n_steps * 1e6, "tokens_per_s": cfg.batch * n_steps / dt,
+            "bound": "hbm", "achieved_gbs": (w_bytes + s_bytes) / (dt / n_steps) / 1e9,
+            "frac": (w_bytes + s_bytes) / (dt / n_steps) / 1e9 / PEAK_HBM_GBS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,6 +109,8 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--no-step", action="store_true",
+                    help="skip the extra rom_step measurement (256 sequences x 512 steps, cfg4)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (a kernel of known traffic, for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -171,6 +203,8 @@ def main():
         "roofline": roofline,
         "stages": stages,
     }
+    if not args.no_step:
+        result["decode_step"] = decode_step_rate()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_tokens)
     print(json.dumps(result))

@@ -38,22 +38,30 @@ struct TileCoord {
   bool valid;
 };
 
-// logical tile id -> (global row tile, column tile) in patches of PM x PN tiles, column patches
-// first, so that workgroups that run together share A row tiles and W column tiles.
-constexpr int kPatchM = 4, kPatchN = 8;
+// logical tile id -> (global row tile, column tile) in patches of 32 tiles, PM x PN with PN = up
+// to 8 column tiles (fewer when the output is narrower), so that workgroups that run together
+// share activation row tiles and weight column tiles.
+constexpr int kPatchTiles = 32, kPatchNMax = 8;
+constexpr bool kXcdRemap = true;    // hand each XCD (workgroup id mod 8) a contiguous run of tiles
+
+__host__ __device__ __forceinline__ int patch_n_for(int n_tiles) {
+  int pn = 1;
+  while (pn < kPatchNMax && pn < n_tiles) pn *= 2;
+  return pn;
+}
 
 __device__ __forceinline__ TileCoord locate_tile(const GemmArgs &a, int BM, int BN) {
   TileCoord tc;
   tc.valid = false;
   const int n_tiles = (a.N + BN - 1) / BN;
-  const int patches_n = (n_tiles + kPatchN - 1) / kPatchN;
-  // consecutive workgroup ids go round-robin over the 8 XCDs; hand each XCD a contiguous run
+  const int pn = patch_n_for(n_tiles), pm = kPatchTiles / pn;
+  const int patches_n = (n_tiles + pn - 1) / pn;
   const int G = gridDim.x;
   int t = blockIdx.x;
-  if (G % 8 == 0) t = (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8;
-  const int patch = t / (kPatchM * kPatchN), in_patch = t % (kPatchM * kPatchN);
-  const int mt = (patch / patches_n) * kPatchM + in_patch % kPatchM;
-  const int nt = (patch % patches_n) * kPatchN + in_patch / kPatchM;
+  if (kXcdRemap && G % 8 == 0) t = (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8;
+  const int patch = t / kPatchTiles, in_patch = t % kPatchTiles;
+  const int mt = (patch / patches_n) * pm + in_patch % pm;
+  const int nt = (patch % patches_n) * pn + in_patch / pm;
   if (nt >= n_tiles) return tc;
   tc.n0 = nt * BN;
   if (a.offsets == nullptr) {
@@ -458,8 +466,9 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const GemmArgs a) {
 int grid_tiles(const GemmArgs &a, int BM, int BN) {
   const int64_t m_tiles = a.offsets ? (a.M / BM + a.n_groups) : ceil_div(a.M, BM);
   const int64_t n_tiles = ceil_div(a.N, BN);
-  const int64_t patches = ceil_div(m_tiles, kPatchM) * ceil_div(n_tiles, kPatchN);
-  int64_t g = patches * kPatchM * kPatchN;
+  const int pn = patch_n_for(static_cast<int>(n_tiles)), pm = kPatchTiles / pn;
+  const int64_t patches = ceil_div(m_tiles, pm) * ceil_div(n_tiles, pn);
+  int64_t g = patches * kPatchTiles;
   g = ceil_div(g, 8) * 8;
   return static_cast<int>(g);
 }
