@@ -110,6 +110,89 @@ constexpr int kRowChunks = kBK / 8;
 // pairs; (r & 7) ^ ((r >> 3) & 1) does that and stays conflict-free on 8-row groups as well.
 __device__ __forceinline__ int lds_swizzle(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 
+// Epilogue shared by the MFMA kernels.  The weight fragment is the MFMA's row operand, so a lane
+// holds, for ONE output row (tile row lane%32), the output columns 8*q + 4*(lane/32) + r of each
+// 32-wide tile in accumulator element 4*q + r: four consecutive columns per q.
+template <int EPI, int TM, int TN, int WTM, int WTN>
+__device__ __forceinline__ void mfma_epilogue(const GemmArgs &a, const TileCoord &tc, f32x16_t (&acc)[TM][TN],
+                                              uint4 *smem, int wave, int wm, int wn, int lane) {
+  const int frag_row = lane & 31, frag_half = lane >> 5;
+  if constexpr (EPI == kEpiPlainF32) {
+    // fp32 output: one 16-byte store per q straight from the accumulators
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int64_t p = tc.row0 + wm * WTM + i * 32 + frag_row;
+      const bool row_ok = p < tc.row_end;
+      const int64_t crow = row_ok ? (a.c_rows ? a.c_rows[p] : p) : 0;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int col = tc.n0 + wn * WTN + j * 32 + q * 8 + frag_half * 4;
+          if (row_ok && col < a.N)
+            *reinterpret_cast<float4 *>(static_cast<float *>(a.C) + blockIdx.y * a.c_split_stride +
+                                        crow * a.ldc + col) =
+                make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        }
+      }
+    }
+  } else {
+    // bf16 output: every wave parks its sub-tile (after bias / softplus / row scale) in its own
+    // slice of the now idle LDS, then writes it out row by row, 16 bytes per lane, so that each
+    // store instruction covers whole 128..256-byte row segments.  No workgroup barrier is needed:
+    // after the last slab's barrier nobody reads the operand buffers for real any more.
+    constexpr int kPitch = WTN * 2 + 16;                 // bytes per parked row (16-byte aligned)
+    char *stage = reinterpret_cast<char *>(smem) + wave * (WTM * kPitch);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      float scale = 1.0f;
+      if (EPI == kEpiRowScale) {
+        const int64_t p = tc.row0 + wm * WTM + i * 32 + frag_row;
+        scale = p < tc.row_end ? a.row_scale[a.c_rows ? a.c_rows[p] : p] : 0.0f;
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int lcol = j * 32 + q * 8 + frag_half * 4;
+          float v[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
+          if (EPI == kEpiBiasSoftplus) {
+            const int col = tc.n0 + wn * WTN + lcol;
+            float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (col < a.N) b4 = *reinterpret_cast<const float4 *>(a.bias + col);
+            v[0] = softplus_fast(v[0] + b4.x); v[1] = softplus_fast(v[1] + b4.y);
+            v[2] = softplus_fast(v[2] + b4.z); v[3] = softplus_fast(v[3] + b4.w);
+          }
+          if (EPI == kEpiRowScale) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] *= scale;
+          }
+          uint2 pk;
+          pk.x = pack_bf16x2(v[0], v[1]);
+          pk.y = pack_bf16x2(v[2], v[3]);
+          *reinterpret_cast<uint2 *>(stage + (i * 32 + frag_row) * kPitch + lcol * 2) = pk;
+        }
+      }
+    }
+    constexpr int kChunks = WTN / 8;                     // 16-byte chunks per parked row
+    constexpr int kRowsPerPass = 64 / kChunks;
+    const int chunk = lane % kChunks, sub = lane / kChunks;
+    const int col = tc.n0 + wn * WTN + chunk * 8;
+#pragma unroll 4
+    for (int r0 = 0; r0 < WTM; r0 += kRowsPerPass) {
+      const int row = r0 + sub;
+      const int64_t p = tc.row0 + wm * WTM + row;
+      if (p < tc.row_end && col < a.N) {
+        const int64_t crow = a.c_rows ? a.c_rows[p] : p;
+        const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * kPitch + chunk * 16);
+        *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.C) + crow * a.ldc + col) = v;
+      }
+    }
+  }
+}
+
 // Scheduling hints for one 16-wide step: after MFMA number I, one LDS fragment read (while there
 // are any) and this MFMA's share of the LDS writes that park the next slab.
 template <int MMA, int READS, int PARKS, bool WITH_PARKS, int I> struct InterleaveHints {
@@ -331,83 +414,142 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
   }
   if (kt < KT) slab(kt, Set0{});
 
-  // epilogue.  The weight fragment is the MFMA's row operand, so a lane holds, for ONE output row
-  // (tile row lane%32), the output columns 8*q + 4*(lane/32) + r of each 32-wide tile in
-  // accumulator element 4*q + r: four consecutive columns per q.
-  if constexpr (EPI == kEpiPlainF32) {
-    // fp32 output: one 16-byte store per q straight from the accumulators
+  mfma_epilogue<EPI, TM, TN, WTM, WTN>(a, tc, acc, smem, wave, wm, wn, lane);
+}
+
+// ------------------------------------------------------------------ bf16 MFMA kernel, LDS-DMA loads
+// Same 256x256 tile and 4x2 wavefront layout, but the operand slabs travel from global memory
+// straight into LDS (global_load_lds_dwordx4: lane l of a wave deposits its 16 bytes at M0 + 16 l),
+// so no registers, no LDS-write instructions and no load->store dependency sit in the MFMA loop.
+// K is walked in 64-wide slabs so that every row contributes one whole 128-byte cache line per
+// slab.  A slab is two "half slabs" of 32 KiB (the 256 A rows, then the 256 W rows) and LDS is a
+// ring of five such slots: while slab m (two slots) is multiplied, A(m+1), W(m+1) and A(m+2) are in
+// flight or landed; the barrier before the last 16-wide step of slab m frees its two slots, which
+// then receive W(m+2) and A(m+3).
+// The XOR swizzle is applied on the global side: the lane that fills 16-byte position c' of row r
+// fetches chunk c' ^ ((r >> 1) & 7), which keeps the 16-lane fragment reads conflict-free for
+// 128-byte rows.  The compiler does not see these loads (inline asm), so the waits are explicit:
+// every wave issues exactly four loads per half slab, in ring order, and "vmcnt(4)" therefore
+// means "everything but the newest half slab I asked for has landed".
+constexpr int kDmaBK = 64, kDmaRC = kDmaBK / 8, kDmaSlots = 5;
+constexpr bool kUseDma = true;
+
+__device__ __forceinline__ void dma_load_16(unsigned lds_addr, unsigned voff, const void *base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n"
+               :: "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
+}
+
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a) {
+  constexpr int BM = 256, BN = 256, WM = 4, WN = 2;
+  static_assert(BM == BN, "a ring slot holds either operand");
+  constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
+  constexpr int kSlotChunks = BM * kDmaRC;                    // 16-byte chunks per ring slot
+  constexpr int kSlotBytes = kSlotChunks * 16;                // 32 KiB
+
+  extern __shared__ __attribute__((aligned(16))) uint4 smem[];
+  const TileCoord tc = locate_tile(a, BM, BN);
+  if (!tc.valid) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WM, wn = wave / WM;
+  const bf16_t *Ap = static_cast<const bf16_t *>(a.A);
+  const bf16_t *Wp = static_cast<const bf16_t *>(a.W) + static_cast<int64_t>(tc.group) * a.N * a.K;
+
+  // this lane's share of a half slab: one 16-byte chunk in each of four 8-row groups
+  unsigned a_voff[4], b_voff[4];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int64_t p = tc.row0 + wm * WTM + i * 32 + frag_row;
-      const bool row_ok = p < tc.row_end;
-      const int64_t crow = row_ok ? (a.c_rows ? a.c_rows[p] : p) : 0;
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int col = tc.n0 + wn * WTN + j * 32 + q * 8 + frag_half * 4;
-          if (row_ok && col < a.N)
-            *reinterpret_cast<float4 *>(static_cast<float *>(a.C) + blockIdx.y * a.c_split_stride +
-                                        crow * a.ldc + col) =
-                make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-        }
-      }
-    }
-  } else {
-    // bf16 output: every wave parks its sub-tile (after bias / softplus / row scale) in its own
-    // slice of the now idle LDS, then writes it out row by row, 16 bytes per lane, so that each
-    // store instruction covers whole 128..256-byte row segments.  No workgroup barrier is needed:
-    // after the last slab's barrier nobody reads the operand buffers for real any more.
-    constexpr int kPitch = WTN * 2 + 16;                 // bytes per parked row (16-byte aligned)
-    char *stage = reinterpret_cast<char *>(smem) + wave * (WTM * kPitch);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      float scale = 1.0f;
-      if (EPI == kEpiRowScale) {
-        const int64_t p = tc.row0 + wm * WTM + i * 32 + frag_row;
-        scale = p < tc.row_end ? a.row_scale[a.c_rows ? a.c_rows[p] : p] : 0.0f;
-      }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int lcol = j * 32 + q * 8 + frag_half * 4;
-          float v[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
-          if (EPI == kEpiBiasSoftplus) {
-            const int col = tc.n0 + wn * WTN + lcol;
-            float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (col < a.N) b4 = *reinterpret_cast<const float4 *>(a.bias + col);
-            v[0] = softplus_fast(v[0] + b4.x); v[1] = softplus_fast(v[1] + b4.y);
-            v[2] = softplus_fast(v[2] + b4.z); v[3] = softplus_fast(v[3] + b4.w);
-          }
-          if (EPI == kEpiRowScale) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) v[r] *= scale;
-          }
-          uint2 pk;
-          pk.x = pack_bf16x2(v[0], v[1]);
-          pk.y = pack_bf16x2(v[2], v[3]);
-          *reinterpret_cast<uint2 *>(stage + (i * 32 + frag_row) * kPitch + lcol * 2) = pk;
-        }
-      }
-    }
-    constexpr int kChunks = WTN / 8;                     // 16-byte chunks per parked row
-    constexpr int kRowsPerPass = 64 / kChunks;
-    const int chunk = lane % kChunks, sub = lane / kChunks;
-    const int col = tc.n0 + wn * WTN + chunk * 8;
-#pragma unroll 4
-    for (int r0 = 0; r0 < WTM; r0 += kRowsPerPass) {
-      const int row = r0 + sub;
-      const int64_t p = tc.row0 + wm * WTM + row;
-      if (p < tc.row_end && col < a.N) {
-        const int64_t crow = a.c_rows ? a.c_rows[p] : p;
-        const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * kPitch + chunk * 16);
-        *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.C) + crow * a.ldc + col) = v;
-      }
-    }
+  for (int j = 0; j < 4; ++j) {
+    const int r = wave * 32 + j * 8 + (lane >> 3);             // tile row filled by this lane
+    const int c = (lane & 7) ^ ((r >> 1) & 7);                 // global chunk that belongs in its position
+    int64_t p = tc.row0 + r;
+    if (p >= tc.row_end) p = tc.row0;                          // rows past the tile: never stored
+    a_voff[j] = static_cast<unsigned>(((a.a_rows ? a.a_rows[p] : p) * a.lda + c * 8) * 2);
+    const int n = (tc.n0 + r < a.N) ? tc.n0 + r : a.N - 1;
+    b_voff[j] = static_cast<unsigned>((static_cast<int64_t>(n) * a.K + c * 8) * 2);
   }
+  const unsigned lds_base =
+      static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) void *)smem));
+  const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 4096);   // 32 rows of 128 bytes
+  const int KT = a.K / kDmaBK;
+
+  // half slab h: the A rows (h even) or the W rows (h odd) of slab h / 2, into ring slot h % 5
+  auto issue = [&](int h) __attribute__((always_inline)) {
+    const int m = h >> 1;
+    const int sl = m < KT ? m : KT - 1;                        // past the end: harmless reload
+    const unsigned slot = lds_wave + static_cast<unsigned>(h % kDmaSlots) * kSlotBytes;
+    if (h & 1) {
+      const bf16_t *wb = Wp + sl * kDmaBK;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) dma_load_16(slot + j * 1024, b_voff[j], wb);
+    } else {
+      const bf16_t *ab = Ap + sl * kDmaBK;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) dma_load_16(slot + j * 1024, a_voff[j], ab);
+    }
+  };
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  const int frag_row = lane & 31, frag_half = lane >> 5;
+  const int a_base = (wm * WTM + frag_row) * kDmaRC, b_base = (wn * WTN + frag_row) * kDmaRC;
+  const int swz = (frag_row >> 1) & 7;
+  bf16x8_t fa0[TM], fa1[TM], fb0[TN], fb1[TN];
+  auto load_frags = [&](int m, int kk, bf16x8_t(&af)[TM], bf16x8_t(&bfr)[TN]) __attribute__((always_inline)) {
+    const int c = (kk * 2 + frag_half) ^ swz;
+    const uint4 *sa = smem + ((2 * m) % kDmaSlots) * kSlotChunks;
+    const uint4 *sb = smem + ((2 * m + 1) % kDmaSlots) * kSlotChunks;
+    {
+      const uint4 v = sa[a_base + c];
+      af[0] = *reinterpret_cast<const bf16x8_t *>(&v);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const uint4 v = sb[b_base + j * 32 * kDmaRC + c];
+      bfr[j] = *reinterpret_cast<const bf16x8_t *>(&v);
+    }
+#pragma unroll
+    for (int i = 1; i < TM; ++i) {
+      const uint4 v = sa[a_base + i * 32 * kDmaRC + c];
+      af[i] = *reinterpret_cast<const bf16x8_t *>(&v);
+    }
+  };
+  auto mma = [&](const bf16x8_t(&af)[TM], const bf16x8_t(&bfr)[TN]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+    InterleaveHints<TM * TN, TM + TN, 0, false, 0>::run();
+  };
+
+#pragma unroll
+  for (int h = 0; h < kDmaSlots; ++h) issue(h);
+  asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");        // slab 0 is in LDS
+  load_frags(0, 0, fa0, fb0);
+
+  for (int m = 0; m < KT; ++m) {
+    load_frags(m, 1, fa1, fb1);
+    mma(fa0, fb0);
+    load_frags(m, 2, fa0, fb0);
+    mma(fa1, fb1);
+    load_frags(m, 3, fa1, fb1);
+    mma(fa0, fb0);
+    // slab m+1 has landed for everyone and nobody reads slab m from LDS any more
+    asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    issue(2 * m + kDmaSlots);                                            // W(m+2) into the slot of A(m)
+    issue(2 * m + kDmaSlots + 1);                                        // A(m+3) into the slot of W(m)
+    load_frags(m + 1, 0, fa0, fb0);
+    mma(fa1, fb1);
+  }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS is reused by the epilogue
+  mfma_epilogue<EPI, TM, TN, WTM, WTN>(a, tc, acc, smem, wave, wm, wn, lane);
 }
 
 // ------------------------------------------------------------------ plain FMA kernel
@@ -497,11 +639,31 @@ hipError_t launch_mfma(const GemmArgs &a, hipStream_t s) {
 }
 
 template <int EPI>
+hipError_t launch_dma(const GemmArgs &a, hipStream_t s) {
+  constexpr int kSmem = kDmaSlots * 256 * kDmaRC * 16;     // 160 KiB
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<EPI>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_bf16_dma_kernel<EPI>), dim3(grid_tiles(a, 256, 256)), dim3(512), kSmem, s, a);
+  return hipGetLastError();
+}
+
+template <int EPI>
 hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
   const int64_t rows_per_group = a.M / (a.n_groups > 0 ? a.n_groups : 1);
   // a short inner dimension makes the launch epilogue-bound: smaller tiles put several
   // workgroups on a CU so that loads, MFMAs and stores of different tiles overlap
-  if (rows_per_group >= 1024 && a.N >= 256 && a.K > 256) return launch_mfma<256, 256, 4, 2, EPI>(a, s);
+  if (rows_per_group >= 1024 && a.N >= 256 && a.K > 256) {
+    // the DMA kernel addresses both operands with unsigned 32-bit byte offsets
+    if (kUseDma && a.K % kDmaBK == 0 && a.k_splits == 1 && a.lda >= a.K && a.a_span < (1ll << 31) &&
+        static_cast<int64_t>(a.N) * a.K < (1ll << 31))
+      return launch_dma<EPI>(a, s);
+    return launch_mfma<256, 256, 4, 2, EPI>(a, s);
+  }
   if (rows_per_group >= 96) return launch_mfma<128, 128, 2, 2, EPI>(a, s);
   return launch_mfma<64, 128, 2, 2, EPI>(a, s);
 }
