@@ -9,11 +9,29 @@ namespace rom {
 namespace {
 
 // ------------------------------------------------------------------ small vector helpers
+// Global loads of 8 / 16 bytes go through native vector types:
+// assigning HIP's uint4 / float4 structs from memory is a memcpy into the register struct, which
+// keeps a struct that lives across the tile loop in scratch memory.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4v_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld_u4(const void *p) {
+  const u32x4_t v = *static_cast<const u32x4_t *>(p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 ld_u2(const void *p) {
+  const u32x2_t v = *static_cast<const u32x2_t *>(p);
+  return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ float4 ld_f4(const void *p) {
+  const f32x4v_t v = *static_cast<const f32x4v_t *>(p);
+  return make_float4(v.x, v.y, v.z, v.w);
+}
 template <typename T> struct Chunk;           // 16 bytes of T
 template <> struct Chunk<bf16_t> {
   static constexpr int kElems = 8;
   uint4 raw;
-  __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const uint4 *>(p); }
+  __device__ __forceinline__ void load(const bf16_t *p) { raw = ld_u4(p); }
   __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<uint4 *>(p) = raw; }
   __device__ __forceinline__ float get(int i) const {
     const unsigned int w = (&raw.x)[i >> 1];
@@ -26,7 +44,7 @@ template <> struct Chunk<bf16_t> {
 template <> struct Chunk<float> {
   static constexpr int kElems = 4;
   float4 raw;
-  __device__ __forceinline__ void load(const float *p) { raw = *reinterpret_cast<const float4 *>(p); }
+  __device__ __forceinline__ void load(const float *p) { raw = ld_f4(p); }
   __device__ __forceinline__ void store(float *p) const { *reinterpret_cast<float4 *>(p) = raw; }
   __device__ __forceinline__ float get(int i) const { return (&raw.x)[i]; }
   __device__ __forceinline__ void set_pair(int i, float lo, float hi) {
@@ -178,19 +196,23 @@ __global__ __launch_bounds__(256) void conv_silu_kernel(
 // sequence chunk and walks it once; the 16 states of a channel live in registers, one per lane.
 // Work is cut into tiles of kScanTile steps and groups of 16 steps:
 //   * the block fetches a tile of dt, u, z (16 channels wide) and of B_t, C_t with 8/16-byte
-//     loads one tile ahead of use (registers), then parks it in double-buffered LDS;
+//     loads one tile ahead of use (registers) and parks it in LDS once the tile before it is done
+//     with (one tile in LDS: 24 KiB per block, so that six blocks fit a CU);
 //     B/C are stored transposed so that lane n reads B_{t,n}, C_{t,n} of four steps at once;
 //   * lane n of a channel picks up dt, u, z of step n of a group and hands dt and dt*u round
 //     with DPP row broadcasts;
 //   * the 16 products C_n*h_n of 16 steps are summed by a transposing butterfly (15 DPP adds per
 //     step pair instead of a full reduction per step) that leaves y of step n in lane n, which
-//     then applies the D skip and the SiLU(z) gate; g leaves through LDS in 4-channel packets.
-// A single wavefront per SIMD issues plain ALU instructions at well under half rate, and one
-// sequence of 4096 channels is exactly one wavefront per SIMD.  Short batches are therefore cut
-// into n_chunks time chunks: a state-only pass (kStateOnly: no C, z, reduction or output) runs
-// every chunk but the last from a zero state and leaves its end state q and total decay
-// P = exp(A * sum dt); the full pass then starts chunk c from the fold h <- P_k h + q_k over the
-// chunks before it.  The recurrence is linear in h, so this is the same arithmetic regrouped.
+//     then applies the D skip and the SiLU(z) gate and writes g over the z it has just read;
+//     g leaves LDS in 4-channel packets.
+// The kernel is bound by plain ALU issue (about ten issue slots per step and lane, the
+// exponential counting for several).  One sequence of 4096 channels is exactly one wavefront per
+// SIMD, which issues at a lower rate than several would; launches with fewer workgroups than CUs
+// are therefore cut into n_chunks time chunks: a state-only pass (kStateOnly: no C, z, reduction
+// or output) runs every chunk but the last from a zero state and leaves its end state q and total
+// decay P = exp(A * sum dt); the full pass then starts chunk c from the fold h <- P_k h + q_k over
+// the chunks before it.  The recurrence is linear in h, so this is the same arithmetic regrouped.
+// Beyond one workgroup per CU the state-only pass costs as much as the better issue rate gains.
 constexpr int kScanTile = 64;
 constexpr int kScanGroups = kScanTile / 16;
 constexpr int kScanCh = 16;
@@ -211,11 +233,10 @@ constexpr int kDppRowBcast0 = 0x150;    // row_newbcast:0 (+j for lane j of the 
 constexpr int kChPitch = kScanCh + 4;
 
 struct __attribute__((aligned(16))) ScanSmem {
-  float dt[2][kScanTile][kChPitch];
-  float u[2][kScanTile][kChPitch];
-  float z[2][kScanTile][kChPitch];
-  float bc[2][32][kBcPitch];            // [buffer][B_0..B_15, C_0..C_15][step]
-  float g[2][kScanTile][kChPitch];
+  float dt[kScanTile][kChPitch];
+  float u[kScanTile][kChPitch];
+  float zg[kScanTile][kChPitch];        // z on the way in; the lane that read z_t puts g_t in its place
+  float bc[32][kBcPitch];               // [B_0..B_15, C_0..C_15][step]
 };
 
 template <int J> struct StepSeq {
@@ -280,7 +301,7 @@ __device__ __forceinline__ float bf16_word_get(unsigned int w, int odd) {
 }
 template <> struct Pack<bf16_t, 8> {
   uint4 raw;
-  __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const uint4 *>(p); }
+  __device__ __forceinline__ void load(const bf16_t *p) { raw = ld_u4(p); }
   __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
   __device__ __forceinline__ void park(float *p) const {      // as floats, 16-byte aligned
     *reinterpret_cast<float4 *>(p) = make_float4(bf16_word_get(raw.x, 0), bf16_word_get(raw.x, 1),
@@ -291,7 +312,7 @@ template <> struct Pack<bf16_t, 8> {
 };
 template <> struct Pack<bf16_t, 4> {
   uint2 raw;
-  __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const uint2 *>(p); }
+  __device__ __forceinline__ void load(const bf16_t *p) { raw = ld_u2(p); }
   __device__ __forceinline__ void zero() { raw = make_uint2(0, 0); }
   __device__ __forceinline__ void park(float *p) const {
     *reinterpret_cast<float4 *>(p) = make_float4(bf16_word_get(raw.x, 0), bf16_word_get(raw.x, 1),
@@ -306,8 +327,8 @@ template <> struct Pack<bf16_t, 4> {
 template <> struct Pack<float, 8> {
   float4 lo, hi;
   __device__ __forceinline__ void load(const float *p) {
-    lo = *reinterpret_cast<const float4 *>(p);
-    hi = *reinterpret_cast<const float4 *>(p + 4);
+    lo = ld_f4(p);
+    hi = ld_f4(p + 4);
   }
   __device__ __forceinline__ void zero() { lo = make_float4(0.f, 0.f, 0.f, 0.f); hi = lo; }
   __device__ __forceinline__ void park(float *p) const {
@@ -317,7 +338,7 @@ template <> struct Pack<float, 8> {
 };
 template <> struct Pack<float, 4> {
   float4 raw;
-  __device__ __forceinline__ void load(const float *p) { raw = *reinterpret_cast<const float4 *>(p); }
+  __device__ __forceinline__ void load(const float *p) { raw = ld_f4(p); }
   __device__ __forceinline__ void zero() { raw = make_float4(0.f, 0.f, 0.f, 0.f); }
   __device__ __forceinline__ void park(float *p) const { *reinterpret_cast<float4 *>(p) = raw; }
   __device__ __forceinline__ void from_floats(const float4 &v) { raw = v; }
@@ -345,9 +366,9 @@ __device__ __forceinline__ void scan_fetch(ScanStage<T> &r, const T *dt_b, const
   if (!kTail || t_z < t_end) {
     if (!kStateOnly) r.z.load(z_b + t_z * ld_z + (tid & 3) * 4);
     if (want_bc) {
-      const float4 *src = reinterpret_cast<const float4 *>(bc_b + t_z * 32 + (tid & 3) * 8);
-      r.bc0 = src[0];
-      r.bc1 = src[1];
+      const float *src = bc_b + t_z * 32 + (tid & 3) * 8;
+      r.bc0 = ld_f4(src);
+      r.bc1 = ld_f4(src + 4);
     }
   } else {
     if (!kStateOnly) r.z.zero();
@@ -357,17 +378,16 @@ __device__ __forceinline__ void scan_fetch(ScanStage<T> &r, const T *dt_b, const
 }
 
 template <typename T, bool kStateOnly>
-__device__ __forceinline__ void scan_park(ScanSmem &sm, int buf, const ScanStage<T> &r, int tid) {
-  r.du.park((tid < 128 ? &sm.dt[buf][0][0] : &sm.u[buf][0][0]) + ((tid & 127) >> 1) * kChPitch +
-            (tid & 1) * 8);
+__device__ __forceinline__ void scan_park(ScanSmem &sm, const ScanStage<T> &r, int tid) {
+  r.du.park((tid < 128 ? &sm.dt[0][0] : &sm.u[0][0]) + ((tid & 127) >> 1) * kChPitch + (tid & 1) * 8);
   const int row = tid >> 2, part = tid & 3;
-  if (!kStateOnly) r.z.park(&sm.z[buf][row][part * 4]);
+  if (!kStateOnly) r.z.park(&sm.zg[row][part * 4]);
   if (!kStateOnly || part < 2) {
     const int col = part * 8;
-    sm.bc[buf][col + 0][row] = r.bc0.x; sm.bc[buf][col + 1][row] = r.bc0.y;
-    sm.bc[buf][col + 2][row] = r.bc0.z; sm.bc[buf][col + 3][row] = r.bc0.w;
-    sm.bc[buf][col + 4][row] = r.bc1.x; sm.bc[buf][col + 5][row] = r.bc1.y;
-    sm.bc[buf][col + 6][row] = r.bc1.z; sm.bc[buf][col + 7][row] = r.bc1.w;
+    sm.bc[col + 0][row] = r.bc0.x; sm.bc[col + 1][row] = r.bc0.y;
+    sm.bc[col + 2][row] = r.bc0.z; sm.bc[col + 3][row] = r.bc0.w;
+    sm.bc[col + 4][row] = r.bc1.x; sm.bc[col + 5][row] = r.bc1.y;
+    sm.bc[col + 6][row] = r.bc1.z; sm.bc[col + 7][row] = r.bc1.w;
   }
 }
 
@@ -420,11 +440,10 @@ __global__ __launch_bounds__(256) void scan_kernel(
     scan_fetch<T, kStateOnly, false>(st, dt_b, u_b, z_b, bc_b, t_begin, t_end, d_inner, ld_z, tid);
   else
     scan_fetch<T, kStateOnly, true>(st, dt_b, u_b, z_b, bc_b, t_begin, t_end, d_inner, ld_z, tid);
-  scan_park<T, kStateOnly>(sm, 0, st, tid);
+  scan_park<T, kStateOnly>(sm, st, tid);
   __syncthreads();
 
   for (int64_t ti = 0; ti < n_tiles; ++ti) {
-    const int buf = static_cast<int>(ti & 1);
     const int64_t t0 = t_begin + ti * kScanTile;
     const bool has_next = ti + 1 < n_tiles;
     if (has_next) {     // next tile's inputs travel while this tile is computed
@@ -433,16 +452,18 @@ __global__ __launch_bounds__(256) void scan_kernel(
       else
         scan_fetch<T, kStateOnly, true>(st, dt_b, u_b, z_b, bc_b, t0 + kScanTile, t_end, d_inner, ld_z, tid);
     }
-#pragma unroll
+    // the state-only pass is one long dependency chain with little else to do: unrolled over the
+    // groups, the scheduler hoists every exponential of the tile and runs out of registers
+#pragma unroll(kStateOnly ? 1 : kScanGroups)
     for (int gi = 0; gi < kScanGroups; ++gi) {
       const int s0 = gi * 16;
-      const float dt_r = sm.dt[buf][s0 + n][cl];
-      const float u_r = sm.u[buf][s0 + n][cl];
+      const float dt_r = sm.dt[s0 + n][cl];
+      const float u_r = sm.u[s0 + n][cl];
       const float dtu_r = dt_r * u_r;
       float bv[16], hs[16];
 #pragma unroll
       for (int j = 0; j < 16; j += 4) {
-        const float4 b4 = *reinterpret_cast<const float4 *>(&sm.bc[buf][n][s0 + j]);
+        const float4 b4 = *reinterpret_cast<const float4 *>(&sm.bc[n][s0 + j]);
         bv[j] = b4.x; bv[j + 1] = b4.y; bv[j + 2] = b4.z; bv[j + 3] = b4.w;
       }
       StepSeq<15>::run(dt_r, dtu_r, a2, bv, h, hs);
@@ -452,24 +473,27 @@ __global__ __launch_bounds__(256) void scan_kernel(
         float cv[16];
 #pragma unroll
         for (int j = 0; j < 16; j += 4) {
-          const float4 c4 = *reinterpret_cast<const float4 *>(&sm.bc[buf][16 + n][s0 + j]);
+          const float4 c4 = *reinterpret_cast<const float4 *>(&sm.bc[16 + n][s0 + j]);
           cv[j] = c4.x; cv[j + 1] = c4.y; cv[j + 2] = c4.z; cv[j + 3] = c4.w;
         }
-        const float z_r = sm.z[buf][s0 + n][cl];
+        const float z_r = sm.zg[s0 + n][cl];
         const float y = transpose_reduce16(hs, cv, n) + d_skip * u_r;
-        sm.g[buf][s0 + n][cl] = y * silu_f32(z_r);
+        sm.zg[s0 + n][cl] = y * silu_f32(z_r);
       }
     }
-    if (has_next) scan_park<T, kStateOnly>(sm, buf ^ 1, st, tid);
-    __syncthreads();
-    if (!kStateOnly) {   // g of this tile: thread -> (step row, 4 channels)
+    __syncthreads();     // everyone is done reading the tile; g is complete
+    if (!kStateOnly) {   // g of this tile: thread -> (step row, 4 channels), the packet it parks z into
       const int r = tid >> 2, q = (tid & 3) * 4;
       const int64_t t = t0 + r;
       if (t < t_end) {
         Pack<T, 4> pk;
-        pk.from_floats(*reinterpret_cast<const float4 *>(&sm.g[buf][r][q]));
+        pk.from_floats(*reinterpret_cast<const float4 *>(&sm.zg[r][q]));
         pk.store(g_b + t * d_inner + q);
       }
+    }
+    if (has_next) {
+      scan_park<T, kStateOnly>(sm, st, tid);
+      __syncthreads();
     }
   }
   if (kStateOnly) {
