@@ -67,7 +67,7 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   p.xz = take(N * 2 * De * b);
   p.xz_sorted = multi ? take(S * 2 * De * b) : kNone;
   p.u = take(N * De * b);
-  p.xdbl = take((routed_xdt ? S : N) * (R + 32) * 4 * xproj_k_splits(routed_xdt ? S : N, d->d_inner));
+  p.xdbl = take((routed_xdt ? S : N) * (R + 32) * 4 * xproj_k_splits(routed_xdt ? S : N, routed_xdt ? d->n_experts : 1, d->d_inner));
   p.dt_low = take(N * R * b);
   p.bc = take(N * 32 * 4);
   p.dt = take(N * De * b);
@@ -193,7 +193,7 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   ga.W = w->w_x; ga.N = R + 32; ga.K = De;
   ga.C = at(p.xdbl); ga.ldc = R + 32; ga.c_is_f32 = 1;
   const int64_t x_rows = routed_xdt ? S : N;
-  ga.k_splits = xproj_k_splits(x_rows, De);
+  ga.k_splits = xproj_k_splits(x_rows, routed_xdt ? E : 1, De);
   {   // the slice length is rounded up to whole 64-wide slabs: use the slice count that results
     const int64_t per = ceil_div(ceil_div(De, ga.k_splits), 64) * 64;
     ga.k_splits = static_cast<int>(ceil_div(De, per));

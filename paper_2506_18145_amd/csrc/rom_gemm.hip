@@ -17,18 +17,22 @@ namespace rom {
 
 namespace {
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 
 __device__ __forceinline__ float softplus_f32(float v) { return v > 20.0f ? v : log1pf(__expf(v)); }
-// branch-free softplus for the bf16 epilogue: log(1 + e) by its series where 1 + e would round
-// (relative error < 1e-5, far below the bf16 rounding of the stored result)
+// branch-free softplus for the bf16 epilogues: max(v, 0) + log(1 + e) with e = exp(-|v|) in (0, 1].
+// Where 1 + e would lose e to rounding, log(1 + e) = e - e^2/2 + ... is replaced by e itself; at the
+// switch point (e = 2^-12) either form is within 1.3e-4 relative of the true value, an order of
+// magnitude below the bf16 rounding of the stored result.  The raw exp2 / log2 instructions are used
+// on purpose: their arguments are never denormal here, so the library's range fix-ups are dead weight
+// in an epilogue that is bound by ALU issue.
 __device__ __forceinline__ float softplus_fast(float v) {
-  const float e = __expf(fminf(v, 20.0f));
-  const float series = e * (1.0f - e * (0.5f - e * 0.333333333f));
-  const float full = __logf(1.0f + e);
-  const float r = e < 0.03f ? series : full;
-  return v > 20.0f ? v : r;
+  const float e = __builtin_amdgcn_exp2f(-1.44269504088896341f * fabsf(v));
+  const float lg = __builtin_amdgcn_logf(1.0f + e) * 0.693147180559945309f;
+  return fmaxf(v, 0.0f) + (e < 2.44140625e-4f ? e : lg);
 }
 
 struct TileCoord {
@@ -433,6 +437,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
 // means "everything but the newest half slab I asked for has landed".
 constexpr int kDmaBK = 64, kDmaRC = kDmaBK / 8, kDmaSlots = 5;
 constexpr bool kUseDma = true;
+constexpr int kSkinnyMinWgs = 200;
+constexpr bool kUseSmallK = true;
 
 __device__ __forceinline__ void dma_load_16(unsigned lds_addr, unsigned voff, const void *base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n"
@@ -552,6 +558,109 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a) {
   mfma_epilogue<EPI, TM, TN, WTM, WTN>(a, tc, acc, smem, wave, wm, wn, lane);
 }
 
+// ------------------------------------------------------------------ bf16 MFMA kernel, short inner dimension
+// For K <= 128 (the dt projection: K = dt_rank) there is no K loop to pipeline: a tile of the
+// general kernel is one load, a few MFMAs and a long epilogue in sequence, and the epilogue
+// (bias + softplus, two transcendentals per element) is bound by plain ALU issue, which needs
+// about four wavefronts per SIMD to run at full rate.  Here a workgroup of eight waves keeps its
+// 128-column slice of W (all of K) and of the bias in LDS and the waves stream 32-row sub-tiles of
+// A past it: A fragments come straight from global memory into registers, each 32x64 half of the
+// result goes through bias + softplus into the wave's own LDS patch and leaves as whole 128-byte
+// row segments.  No workgroup barrier after the W load; registers are capped at 128 so that two
+// workgroups (16 waves) share a CU.
+constexpr int kSkBM = 512, kSkBN = 128, kSkWaves = 8;
+
+template <int KSTEPS>
+__global__ __launch_bounds__(kSkWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 8)))
+void gemm_bf16_smallk_kernel(const GemmArgs a) {
+  constexpr int KC = KSTEPS * 2;                       // 16-byte chunks per row of A / W
+  static_assert(KC == 4 || KC == 8 || KC == 16, "K must be 32, 64 or 128");
+  constexpr int kSwzShift = KC == 16 ? 0 : (KC == 8 ? 1 : 2);   // 16 consecutive rows -> 16 distinct 16-byte banks
+  constexpr int kHalf = kSkBN / 2;                     // columns per pass over the accumulators
+  constexpr int kPitch = kHalf * 2 + 16;               // bytes per staged output row; the pad holds its C row index
+
+  extern __shared__ __attribute__((aligned(16))) uint4 smem[];
+  const TileCoord tc = locate_tile(a, kSkBM, kSkBN);
+  if (!tc.valid) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bf16_t *Ap = static_cast<const bf16_t *>(a.A);
+  const bf16_t *Wp = static_cast<const bf16_t *>(a.W) + static_cast<int64_t>(tc.group) * a.N * a.K;
+  uint4 *Ws = smem;                                                        // [128][KC], swizzled
+  float *bias_s = reinterpret_cast<float *>(smem + kSkBN * KC);            // [128]
+  char *stage = reinterpret_cast<char *>(bias_s + kSkBN) + wave * (32 * kPitch);
+
+  for (int q = tid; q < kSkBN * KC; q += kSkWaves * 64) {
+    const int r = q / KC, c = q % KC;
+    const int n = (tc.n0 + r < a.N) ? tc.n0 + r : a.N - 1;
+    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(Wp + static_cast<int64_t>(n) * a.K + c * 8);
+    Ws[r * KC + (c ^ ((r >> kSwzShift) & (KC - 1)))] = make_uint4(v.x, v.y, v.z, v.w);
+  }
+  if (tid < kSkBN) bias_s[tid] = a.bias[(tc.n0 + tid < a.N) ? tc.n0 + tid : a.N - 1];
+  __syncthreads();
+
+  const int frag_row = lane & 31, frag_half = lane >> 5;
+  const int swz = (frag_row >> kSwzShift) & (KC - 1);
+  const int n_sub = static_cast<int>((tc.row_end - tc.row0 + 31) / 32);
+  const int chunk = lane & 7, sub_row = lane >> 3;     // store phase: 8 rows x 128 bytes per instruction
+
+  for (int sub = wave; sub < n_sub; sub += kSkWaves) {
+    // A fragment: row frag_row of the sub-tile, 8 elements at K offset 16 kk + 8 frag_half
+    int64_t p = tc.row0 + sub * 32 + frag_row;
+    if (p >= tc.row_end) p = tc.row0;                 // rows past the tile: computed, never stored
+    const int64_t ar = a.a_rows ? a.a_rows[p] : p;
+    const int crow = static_cast<int>(a.c_rows ? a.c_rows[p] : p);
+    const bf16_t *src = Ap + ar * a.lda + frag_half * 8;
+    bf16x8_t af[KSTEPS];
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) af[kk] = *reinterpret_cast<const bf16x8_t *>(src + kk * 16);
+    if (frag_half == 0) *reinterpret_cast<int *>(stage + frag_row * kPitch + kHalf * 2) = crow;
+
+#pragma unroll 1
+    for (int h = 0; h < 2; ++h) {
+      f32x16_t acc[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+#pragma unroll
+      for (int kk = 0; kk < KSTEPS; ++kk) {
+        const int c = (kk * 2 + frag_half) ^ swz;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const uint4 w = Ws[(h * kHalf + j * 32 + frag_row) * KC + c];
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t *>(&w), af[kk], acc[j], 0, 0, 0);
+        }
+      }
+      // W is the MFMA's row operand: this lane holds, for A row frag_row, the output columns
+      // 32 j + 8 q + 4 frag_half + r of this half in acc[j][4 q + r]
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int lcol = j * 32 + q * 8 + frag_half * 4;
+          const float4 b4 = *reinterpret_cast<const float4 *>(bias_s + h * kHalf + lcol);
+          uint2 pk;
+          pk.x = pack_bf16x2(softplus_fast(acc[j][4 * q] + b4.x), softplus_fast(acc[j][4 * q + 1] + b4.y));
+          pk.y = pack_bf16x2(softplus_fast(acc[j][4 * q + 2] + b4.z), softplus_fast(acc[j][4 * q + 3] + b4.w));
+          *reinterpret_cast<uint2 *>(stage + frag_row * kPitch + lcol * 2) = pk;
+        }
+      }
+      // the wave's own patch: LDS serves one wave's accesses in program order, no barrier needed
+      const int col = tc.n0 + h * kHalf + chunk * 8;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = i * 8 + sub_row;
+        const int64_t pr = tc.row0 + sub * 32 + row;
+        const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * kPitch + chunk * 16);
+        const int cr = *reinterpret_cast<const int *>(stage + row * kPitch + kHalf * 2);
+        if (pr < tc.row_end && col < a.N)
+          *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.C) + static_cast<int64_t>(cr) * a.ldc + col) = v;
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------ plain FMA kernel
 constexpr int kSB = 64, kSK = 16;       // 64x64 tile, K slab 16, 256 threads, 4x4 per thread
 
@@ -638,6 +747,20 @@ hipError_t launch_mfma(const GemmArgs &a, hipStream_t s) {
   return launch_mfma_k<BM, BN, WM, WN, EPI, true>(a, s);
 }
 
+template <int KSTEPS>
+hipError_t launch_smallk(const GemmArgs &a, hipStream_t s) {
+  constexpr int kSmem = kSkBN * KSTEPS * 2 * 16 + kSkBN * 4 + kSkWaves * 32 * (kSkBN + 16);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_smallk_kernel<KSTEPS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_bf16_smallk_kernel<KSTEPS>), dim3(grid_tiles(a, kSkBM, kSkBN)), dim3(kSkWaves * 64), kSmem, s, a);
+  return hipGetLastError();
+}
+
 template <int EPI>
 hipError_t launch_dma(const GemmArgs &a, hipStream_t s) {
   constexpr int kSmem = kDmaSlots * 256 * kDmaRC * 16;     // 160 KiB
@@ -694,13 +817,16 @@ hipError_t launch_grouped_gemm(const GemmArgs &args, hipStream_t s) {
   }
   if (a.c_is_f32) {
     if (a.N <= 192) {
-      // one column tile: the grid is the number of row tiles, so use 64-row tiles (two waves)
-      // when 128-row tiles would leave CUs without work
-      const bool small_rows = a.M / 128 + a.n_groups < 200;
+      // one column tile: every workgroup re-reads the whole weight slice of its group, so take the
+      // tallest row tile (256 rows on four waves, 128 on four, 64 on two) that still gives the
+      // chip about one workgroup per CU, counting the inner-dimension slices
+      const auto wgs = [&](int rows) { return (a.M / rows + a.n_groups) * a.k_splits; };
+      const int tile_rows = wgs(256) >= kSkinnyMinWgs ? 256 : (wgs(128) >= kSkinnyMinWgs ? 128 : 64);
       switch ((a.N + 31) / 32) {
 #define ROM_SKINNY(NN)                                                               \
-  return small_rows ? launch_mfma<64, NN, 2, 1, kEpiPlainF32>(a, s)                  \
-                    : launch_mfma<128, NN, 4, 1, kEpiPlainF32>(a, s)
+  return tile_rows == 256 ? launch_mfma<256, NN, 4, 1, kEpiPlainF32>(a, s)           \
+       : tile_rows == 128 ? launch_mfma<128, NN, 4, 1, kEpiPlainF32>(a, s)           \
+                          : launch_mfma<64, NN, 2, 1, kEpiPlainF32>(a, s)
         case 1: ROM_SKINNY(32);
         case 2: ROM_SKINNY(64);
         case 3: ROM_SKINNY(96);
@@ -712,7 +838,14 @@ hipError_t launch_grouped_gemm(const GemmArgs &args, hipStream_t s) {
     }
     return launch_mfma_tiles<kEpiPlainF32>(a, s);
   }
-  if (a.bias) return launch_mfma_tiles<kEpiBiasSoftplus>(a, s);
+  if (a.bias) {
+    if (kUseSmallK && a.lda >= a.K && a.M < (1ll << 31)) {
+      if (a.K == 128) return launch_smallk<8>(a, s);
+      if (a.K == 64) return launch_smallk<4>(a, s);
+      if (a.K == 32) return launch_smallk<2>(a, s);
+    }
+    return launch_mfma_tiles<kEpiBiasSoftplus>(a, s);
+  }
   if (a.row_scale) return launch_mfma_tiles<kEpiRowScale>(a, s);
   return launch_mfma_tiles<kEpiPlain>(a, s);
 }

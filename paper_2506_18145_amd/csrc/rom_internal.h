@@ -86,7 +86,7 @@ hipError_t launch_split_xdbl(int dtype, const float *xdbl, int n_slices, int64_t
                              const int32_t *inv_perm, int top_k, int64_t n_tokens, int dt_rank,
                              void *dt_low, float *bc, hipStream_t s);
 // number of inner-dimension slices the x projection is cut into (small batches only)
-int xproj_k_splits(int64_t rows, int d_inner);
+int xproj_k_splits(int64_t rows, int n_groups, int d_inner);
 hipError_t launch_conv_silu(int dtype, const void *xz, int64_t ld_xz, const float *conv_w,
                             const float *conv_b, const float *state_in, float *state_out, void *u,
                             int64_t B, int64_t L, int d_inner, hipStream_t s);

@@ -593,11 +593,15 @@ hipError_t launch_slot_sum(int src_is_f32, int dst_is_f32, const void *src, int6
   return hipGetLastError();
 }
 
-int xproj_k_splits(int64_t rows, int d_inner) {
-  // few rows: the grid of row tiles cannot fill the chip, so cut the long inner dimension instead
-  if (rows > 4096 || d_inner < 1024) return 1;
+int xproj_k_splits(int64_t rows, int n_groups, int d_inner) {
+  // The x projection has a single column tile, so its grid is the number of 256-row tiles, and
+  // the workgroups are bound by what one CU can pull through its L1 (one tile per CU at a time).
+  // Cut the long inner dimension into as many slices as still give at most one workgroup per CU.
   const int by_len = d_inner / 512;
-  return by_len > 8 ? 8 : (by_len < 1 ? 1 : by_len);
+  const int64_t tiles = rows / 256 + n_groups;
+  const int64_t fit = 256 / tiles;
+  const int64_t n = fit < by_len ? fit : by_len;
+  return n > 8 ? 8 : (n < 1 ? 1 : static_cast<int>(n));
 }
 
 hipError_t launch_split_xdbl(int dtype, const float *xdbl, int n_slices, int64_t slice_stride,
