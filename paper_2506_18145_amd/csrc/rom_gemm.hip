@@ -437,7 +437,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
 // means "everything but the newest half slab I asked for has landed".
 constexpr int kDmaBK = 64, kDmaRC = kDmaBK / 8, kDmaSlots = 5;
 constexpr bool kUseDma = true;
-constexpr int kSkinnyMinWgs = 200;
+constexpr int kSkinnyMinWgs = 100;
 constexpr bool kUseSmallK = true;
 
 __device__ __forceinline__ void dma_load_16(unsigned lds_addr, unsigned voff, const void *base) {
@@ -445,13 +445,18 @@ __device__ __forceinline__ void dma_load_16(unsigned lds_addr, unsigned voff, co
                :: "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
 }
 
-template <int EPI>
+// BN < 256 (a single, narrow column tile: the x projection) keeps the 256-row activation tile and
+// the five 32 KiB ring slots; the weight half slabs just fill less of theirs.  grid.y slices the
+// inner dimension (fp32 partial sums, plain epilogue only).
+template <int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a) {
-  constexpr int BM = 256, BN = 256, WM = 4, WN = 2;
-  static_assert(BM == BN, "a ring slot holds either operand");
+  constexpr int BM = 256;
+  static_assert(WM * WN == 8 && BN <= BM && BN % (32 * WN) == 0, "eight waves, 32-wide MFMA tiles");
   constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
   constexpr int kSlotChunks = BM * kDmaRC;                    // 16-byte chunks per ring slot
   constexpr int kSlotBytes = kSlotChunks * 16;                // 32 KiB
+  constexpr int kAInstr = BM / 64;                            // DMA instructions per wave and half slab: 8 rows each
+  constexpr int kWInstr = (BN + 63) / 64;                     // (rows past BN are clamped re-reads into unused slot space)
 
   extern __shared__ __attribute__((aligned(16))) uint4 smem[];
   const TileCoord tc = locate_tile(a, BM, BN);
@@ -459,39 +464,47 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
-  const bf16_t *Ap = static_cast<const bf16_t *>(a.A);
-  const bf16_t *Wp = static_cast<const bf16_t *>(a.W) + static_cast<int64_t>(tc.group) * a.N * a.K;
+  const int k_begin = blockIdx.y * a.k_per_split;
+  const int k_len = (a.K - k_begin < a.k_per_split) ? a.K - k_begin : a.k_per_split;
+  const bf16_t *Ap = static_cast<const bf16_t *>(a.A) + k_begin;
+  const bf16_t *Wp = static_cast<const bf16_t *>(a.W) + static_cast<int64_t>(tc.group) * a.N * a.K + k_begin;
 
-  // this lane's share of a half slab: one 16-byte chunk in each of four 8-row groups
-  unsigned a_voff[4], b_voff[4];
+  // this lane's share of a half slab: one 16-byte chunk in each of its wave's 8-row groups
+  unsigned a_voff[kAInstr], b_voff[kWInstr];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int r = wave * 32 + j * 8 + (lane >> 3);             // tile row filled by this lane
+  for (int j = 0; j < kAInstr; ++j) {
+    const int r = (wave * kAInstr + j) * 8 + (lane >> 3);      // tile row filled by this lane
     const int c = (lane & 7) ^ ((r >> 1) & 7);                 // global chunk that belongs in its position
     int64_t p = tc.row0 + r;
     if (p >= tc.row_end) p = tc.row0;                          // rows past the tile: never stored
     a_voff[j] = static_cast<unsigned>(((a.a_rows ? a.a_rows[p] : p) * a.lda + c * 8) * 2);
+  }
+#pragma unroll
+  for (int j = 0; j < kWInstr; ++j) {
+    const int r = (wave * kWInstr + j) * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
     const int n = (tc.n0 + r < a.N) ? tc.n0 + r : a.N - 1;
     b_voff[j] = static_cast<unsigned>((static_cast<int64_t>(n) * a.K + c * 8) * 2);
   }
   const unsigned lds_base =
       static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) void *)smem));
-  const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 4096);   // 32 rows of 128 bytes
-  const int KT = a.K / kDmaBK;
+  const unsigned lds_wave_a = __builtin_amdgcn_readfirstlane(lds_base + wave * (kAInstr * 1024));
+  const unsigned lds_wave_w = __builtin_amdgcn_readfirstlane(lds_base + wave * (kWInstr * 1024));
+  const int KT = k_len / kDmaBK;
 
   // half slab h: the A rows (h even) or the W rows (h odd) of slab h / 2, into ring slot h % 5
   auto issue = [&](int h) __attribute__((always_inline)) {
     const int m = h >> 1;
     const int sl = m < KT ? m : KT - 1;                        // past the end: harmless reload
-    const unsigned slot = lds_wave + static_cast<unsigned>(h % kDmaSlots) * kSlotBytes;
+    const unsigned slot = static_cast<unsigned>(h % kDmaSlots) * kSlotBytes;
     if (h & 1) {
       const bf16_t *wb = Wp + sl * kDmaBK;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) dma_load_16(slot + j * 1024, b_voff[j], wb);
+      for (int j = 0; j < kWInstr; ++j) dma_load_16(lds_wave_w + slot + j * 1024, b_voff[j], wb);
     } else {
       const bf16_t *ab = Ap + sl * kDmaBK;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) dma_load_16(slot + j * 1024, a_voff[j], ab);
+      for (int j = 0; j < kAInstr; ++j) dma_load_16(lds_wave_a + slot + j * 1024, a_voff[j], ab);
     }
   };
 
@@ -537,7 +550,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a) {
 
 #pragma unroll
   for (int h = 0; h < kDmaSlots; ++h) issue(h);
-  asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");        // slab 0 is in LDS
+  // slab 0 is in LDS once only A(1), W(1), A(2) are outstanding
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * kAInstr + kWInstr) : "memory");
   load_frags(0, 0, fa0, fb0);
 
   for (int m = 0; m < KT; ++m) {
@@ -547,8 +561,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a) {
     mma(fa1, fb1);
     load_frags(m, 3, fa1, fb1);
     mma(fa0, fb0);
-    // slab m+1 has landed for everyone and nobody reads slab m from LDS any more
-    asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // slab m+1 has landed for everyone (only A(m+2) is outstanding) and nobody reads slab m any more
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kAInstr) : "memory");
     issue(2 * m + kDmaSlots);                                            // W(m+2) into the slot of A(m)
     issue(2 * m + kDmaSlots + 1);                                        // A(m+3) into the slot of W(m)
     load_frags(m + 1, 0, fa0, fb0);
@@ -761,18 +775,24 @@ hipError_t launch_smallk(const GemmArgs &a, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int EPI>
+template <int BN, int WM, int WN, int EPI>
 hipError_t launch_dma(const GemmArgs &a, hipStream_t s) {
   constexpr int kSmem = kDmaSlots * 256 * kDmaRC * 16;     // 160 KiB
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<EPI>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<BN, WM, WN, EPI>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_bf16_dma_kernel<EPI>), dim3(grid_tiles(a, 256, 256)), dim3(512), kSmem, s, a);
+  hipLaunchKernelGGL((gemm_bf16_dma_kernel<BN, WM, WN, EPI>), dim3(grid_tiles(a, 256, BN), a.k_splits), dim3(512),
+                     kSmem, s, a);
   return hipGetLastError();
+}
+// the DMA kernel addresses both operands with unsigned 32-bit byte offsets and walks whole 64-wide slabs
+inline bool dma_ok(const GemmArgs &a) {
+  return kUseDma && a.K % kDmaBK == 0 && a.k_per_split % kDmaBK == 0 && a.lda >= a.K &&
+         a.a_span < (1ll << 31) && static_cast<int64_t>(a.N) * a.K < (1ll << 31);
 }
 
 template <int EPI>
@@ -781,10 +801,7 @@ hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
   // a short inner dimension makes the launch epilogue-bound: smaller tiles put several
   // workgroups on a CU so that loads, MFMAs and stores of different tiles overlap
   if (rows_per_group >= 1024 && a.N >= 256 && a.K > 256) {
-    // the DMA kernel addresses both operands with unsigned 32-bit byte offsets
-    if (kUseDma && a.K % kDmaBK == 0 && a.k_splits == 1 && a.lda >= a.K && a.a_span < (1ll << 31) &&
-        static_cast<int64_t>(a.N) * a.K < (1ll << 31))
-      return launch_dma<EPI>(a, s);
+    if (dma_ok(a) && a.k_splits == 1) return launch_dma<256, 4, 2, EPI>(a, s);
     return launch_mfma<256, 256, 4, 2, EPI>(a, s);
   }
   if (rows_per_group >= 96) return launch_mfma<128, 128, 2, 2, EPI>(a, s);
@@ -818,12 +835,13 @@ hipError_t launch_grouped_gemm(const GemmArgs &args, hipStream_t s) {
   if (a.c_is_f32) {
     if (a.N <= 192) {
       // one column tile: every workgroup re-reads the whole weight slice of its group, so take the
-      // tallest row tile (256 rows on four waves, 128 on four, 64 on two) that still gives the
-      // chip about one workgroup per CU, counting the inner-dimension slices
+      // tallest row tile (256 rows, 128 on four waves, 64 on two) that still puts a workgroup on
+      // a good part of the CUs, counting the inner-dimension slices
       const auto wgs = [&](int rows) { return (a.M / rows + a.n_groups) * a.k_splits; };
       const int tile_rows = wgs(256) >= kSkinnyMinWgs ? 256 : (wgs(128) >= kSkinnyMinWgs ? 128 : 64);
       switch ((a.N + 31) / 32) {
 #define ROM_SKINNY(NN)                                                               \
+  if (tile_rows == 256 && dma_ok(a)) return launch_dma<NN, 8, 1, kEpiPlainF32>(a, s); \
   return tile_rows == 256 ? launch_mfma<256, NN, 4, 1, kEpiPlainF32>(a, s)           \
        : tile_rows == 128 ? launch_mfma<128, NN, 4, 1, kEpiPlainF32>(a, s)           \
                           : launch_mfma<64, NN, 2, 1, kEpiPlainF32>(a, s)

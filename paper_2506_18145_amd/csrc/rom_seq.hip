@@ -594,14 +594,24 @@ hipError_t launch_slot_sum(int src_is_f32, int dst_is_f32, const void *src, int6
 }
 
 int xproj_k_splits(int64_t rows, int n_groups, int d_inner) {
-  // The x projection has a single column tile, so its grid is the number of 256-row tiles, and
-  // the workgroups are bound by what one CU can pull through its L1 (one tile per CU at a time).
-  // Cut the long inner dimension into as many slices as still give at most one workgroup per CU.
+  // The x projection has a single column tile, so its grid is the number of 256-row tiles: far
+  // fewer than CUs.  Slicing the long inner dimension shortens every workgroup's slab loop but
+  // each slice writes fp32 partial sums that split_xdbl has to read back.  Pick the slice count
+  // with the smallest estimate  slabs / s * t_slab + s * rows * t_row  (measured on MI355X:
+  // about 0.87 us per 64-wide slab and 12 us per slice at 16384 rows), at most one workgroup per CU.
   const int by_len = d_inner / 512;
   const int64_t tiles = rows / 256 + n_groups;
-  const int64_t fit = 256 / tiles;
-  const int64_t n = fit < by_len ? fit : by_len;
-  return n > 8 ? 8 : (n < 1 ? 1 : static_cast<int>(n));
+  int64_t s_max = 256 / tiles;
+  if (s_max > by_len) s_max = by_len;
+  if (s_max > 8) s_max = 8;
+  const double slabs = d_inner / 64.0, per_slice = 12.0 * static_cast<double>(rows) / 16384.0;
+  int best = 1;
+  double best_t = slabs * 0.87 + per_slice;
+  for (int s = 2; s <= s_max; ++s) {
+    const double t = slabs / s * 0.87 + s * per_slice;
+    if (t < best_t) { best_t = t; best = s; }
+  }
+  return best;
 }
 
 hipError_t launch_split_xdbl(int dtype, const float *xdbl, int n_slices, int64_t slice_stride,
