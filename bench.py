@@ -24,7 +24,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 PEAK_ALU_FP32_TFLOPS = 78.6
 # HBM bytes per in_proj launch at cfg2 from rocprofv3 FETCH_SIZE (x2.0 copy-kernel calibration) +
 # WRITE_SIZE (x1.0): see profiles/forward_cfg2_hbm_traffic.md
-TRAFFIC_IN_PROJ_CFG2_BYTES = (994 + 257) * 2 ** 20
+TRAFFIC_IN_PROJ_CFG2_BYTES = (992 + 256) * 2 ** 20
 
 
 def stage_model(cfg):
@@ -108,7 +108,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
     ap.add_argument("--no-step", action="store_true",
                     help="skip the extra rom_step measurement (256 sequences x 512 steps, cfg4)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -182,7 +182,7 @@ def main():
             ach = work / (avg_ms * 1e-3) / 1e9
             stages[name] = {"ms": avg_ms, "bound": "hbm", "achieved_gbs": ach, "frac": ach / PEAK_HBM_GBS}
     dom = stages["in_proj"]
-    roofline = {"kernel": "in_proj grouped GEMM (gemm_bf16_mfma_kernel)", "bound": "mfma",
+    roofline = {"kernel": "in_proj grouped GEMM (gemm_bf16_dma_kernel<256, 4, 2, 0>)", "bound": "mfma",
                 "achieved": dom.get("achieved_tflops"), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": dom.get("frac"),
                 "traffic": TRAFFIC_IN_PROJ_CFG2_BYTES if cfg.name == "cfg2" else None}
