@@ -49,6 +49,24 @@ def test_small_layers(kw):
     compare_layer(cfg, gpu, x, w)
 
 
+@pytest.mark.parametrize("kw", [
+    # >= 1024 rows per expert: the 256x256 LDS-DMA tiles (in/out projection), the narrow-tile and
+    # split-K variants (x projection) and the short-inner-dimension kernel (dt projection, K = 32 / 64)
+    dict(batch=1, seq_len=5000, d_model=512, d_inner=1024, dt_rank=32, cfg_id=60),
+    dict(batch=2, seq_len=2050, d_model=512, d_inner=1024, dt_rank=64, top_k=2, gate_mode=1, cfg_id=61),
+    # one expert never chosen, one taking most tokens: empty groups and many partial tiles
+    dict(batch=1, seq_len=4999, d_model=512, d_inner=1024, dt_rank=32, cfg_id=62,
+         router_bias=(0.5, 0.0, 0.0, -50.0)),
+    dict(batch=1, seq_len=4500, d_model=320, d_inner=640, dt_rank=64, routed_xdt=False, cfg_id=63),
+])
+def test_medium_layers_big_tile_kernels(kw):
+    cfg = small_cfg(**kw)
+    _, gpu, x, w = run_layer(cfg)
+    if "router_bias" in kw:
+        assert gpu["counts"][3] == 0 and gpu["counts"][0] > cfg.seq_len // 2
+    compare_layer(cfg, gpu, x, w)
+
+
 def test_carried_state_and_split_sequence():
     cfg = small_cfg(seq_len=150, top_k=2, gate_mode=1)
     cs, ss = make_states(cfg)
