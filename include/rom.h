@@ -152,11 +152,13 @@ ROM_API int rom_step(const rom_dims *dims, const rom_weights *w, const void *x, 
 /* Static description of an error code. */
 ROM_API const char *rom_strerror(int code);
 
-/* Per-stage timing for benchmarks.  While enabled, rom_layer_forward and rom_step record
- * HIP events on the launch stream around each stage (kernel or small kernel group).
- * rom_profile_collect synchronises on those events, adds the elapsed milliseconds of every
- * recorded call into stage_ms (host, ROM_STAGE_COUNT doubles), stores the number of calls in
- * *n_calls (host) and resets the recorder.  max_calls == 0 disables recording and frees the events. */
+/* Per-stage timing for benchmarks.  While enabled, rom_layer_forward and rom_step record a pair
+ * of HIP events around each stage (kernel or small kernel group) of each segment (see
+ * rom_set_segments), on the stream the stage is launched on.  rom_profile_collect synchronises on
+ * those events, adds the elapsed milliseconds of every recorded stage into stage_ms (host,
+ * ROM_STAGE_COUNT doubles; with more than one segment stages overlap, so their sum exceeds the
+ * wall time), stores the number of calls in *n_calls (host) and resets the recorder.
+ * max_calls == 0 disables recording and frees the events. */
 #define ROM_STAGE_ROUTE     0  /* router logits, top-K, gates                         */
 #define ROM_STAGE_PERMUTE   1  /* histogram, offsets, stable permutation              */
 #define ROM_STAGE_IN_PROJ   2  /* grouped GEMM, Eq. (10)/(11) (+ sum over k if K > 1)  */
@@ -170,6 +172,19 @@ ROM_API const char *rom_strerror(int code);
 ROM_API int rom_profile_enable(int max_calls);
 ROM_API int rom_profile_collect(double *stage_ms, int *n_calls);
 ROM_API const char *rom_stage_name(int stage);
+
+/* Experimental tuning knob of the forward pass.  A call can be cut into segments (contiguous token
+ * ranges: time ranges of a single sequence, whole sequences otherwise) whose stages after the
+ * permutation run as a software pipeline on the caller's stream and one stream the library owns,
+ * joined back into the caller's stream before the call returns, so that the ALU-bound scan of one
+ * segment shares the CUs with the GEMMs of its neighbours.  Results do not depend on the setting
+ * beyond floating-point regrouping of the conv / scan carry.
+ *   n_segments = 0 or 1: never cut (default: on MI355X the overlap gains nothing measurable),
+ *   2..4: cut every call with L >= 2 into that many segments.
+ * Process-wide; the library's stream and events are per device and shared by all calls on it:
+ * calls that overlap on one device from several host threads race on them.
+ * The workspace size depends on this setting: query rom_workspace_bytes after changing it. */
+ROM_API int rom_set_segments(int n_segments);
 
 #ifdef __cplusplus
 }

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     rom_layer_forward,
     rom_profile_collect,
     rom_profile_enable,
+    rom_set_segments,
     rom_route,
     rom_step,
     rom_workspace_bytes,

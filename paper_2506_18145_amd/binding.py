@@ -65,6 +65,8 @@ def load_library() -> ctypes.CDLL:
     lib.rom_profile_enable.argtypes = [ctypes.c_int]
     lib.rom_profile_collect.restype = ctypes.c_int
     lib.rom_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
+    lib.rom_set_segments.restype = ctypes.c_int
+    lib.rom_set_segments.argtypes = [ctypes.c_int]
     lib.rom_stage_name.restype = ctypes.c_char_p
     lib.rom_stage_name.argtypes = [ctypes.c_int]
     _lib = lib
@@ -130,6 +132,10 @@ def rom_step(dims, weights, x, B, conv_state, ssm_state, out, ws):
         _ptr(ssm_state), _ptr(out), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
         _stream())
     _check(code, "rom_step")
+
+
+def rom_set_segments(n_segments: int) -> None:
+    _check(load_library().rom_set_segments(n_segments), "rom_set_segments")
 
 
 def rom_profile_enable(max_calls: int) -> None:

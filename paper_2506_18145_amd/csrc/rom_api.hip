@@ -10,10 +10,60 @@ namespace {
 constexpr size_t kAlign = 256;
 constexpr size_t kNone = static_cast<size_t>(-1);
 
+// A call can be cut into up to kMaxSegments segments, contiguous token ranges that run the stages
+// after the permutation as a software pipeline on two streams (the caller's and one of the
+// library's), so that the scan of one segment shares the CUs with the GEMMs of its neighbours.
+// One sequence is cut in time (conv and scan state carried from segment to segment), several
+// sequences are dealt out whole.  Routing and the permutation stay global: the permutation is
+// stable, so the slots of a token range are a contiguous sub-range of every expert's group,
+// found by binary search (segment_bounds_kernel).
+// Measured on MI355X at d_model 2048, 16K tokens: co-running kernels slow each other down by
+// what the overlap gains (two segments 1.58 ms against 1.59 ms uncut, more segments are slower),
+// so the automatic setting never cuts; the knob (rom_set_segments) stays for experiments.
+constexpr int kMaxSegments = 4;
+int g_force_segments = 0;            // 0: automatic
+constexpr int kStagger = 1;   // 0: none, 1: a segment starts when the one before has left its conv, 2: ... its dt projection
+
+struct Segments {
+  int n;
+  int64_t tok[kMaxSegments + 1];     // token boundaries, tok[0] = 0, tok[n] = B * L
+  int64_t seq[kMaxSegments + 1];     // sequence boundaries (B > 1) or 0 / 1
+  bool by_time;
+};
+
+Segments plan_segments(const rom_dims *d, int64_t B, int64_t L) {
+  Segments sg;
+  int want = 1;
+  if (g_force_segments > 0) want = g_force_segments;
+  (void)d;
+  if (want > kMaxSegments) want = kMaxSegments;
+  if (L < 2 || B < 1) want = 1;
+  sg.by_time = B == 1;
+  if (sg.by_time) {
+    const int64_t per = ceil_div(ceil_div(L, want), 64) * 64;   // whole scan tiles
+    sg.n = static_cast<int>(ceil_div(L, per));
+    for (int i = 0; i <= sg.n; ++i) {
+      sg.tok[i] = i * per < L ? i * per : L;
+      sg.seq[i] = i == 0 ? 0 : 1;
+    }
+  } else {
+    const int64_t per = ceil_div(B, want);
+    sg.n = static_cast<int>(ceil_div(B, per));
+    for (int i = 0; i <= sg.n; ++i) {
+      sg.seq[i] = i * per < B ? i * per : B;
+      sg.tok[i] = sg.seq[i] * L;
+    }
+  }
+  return sg;
+}
+
 struct Plan {                 // byte offsets inside the workspace
   size_t total;
   size_t expert_idx, gate, counts, offsets, perm, inv_perm, tok_of_pos, block_counts, logits;
-  size_t xz, xz_sorted, u, xdbl, dt_low, bc, dt, dt_raw, g, op_sorted, conv_tmp, scan_q, scan_p;
+  size_t xz, xz_sorted, u, xdbl, dt_low, bc, dt, dt_raw, g, op_sorted, conv_tmp;
+  size_t seg_lo, seg_hi, conv_carry, ssm_carry;
+  size_t scan_q[kMaxSegments], scan_p[kMaxSegments];
+  int xproj_slices;           // inner-dimension slices the xdbl buffer has room for
 };
 
 int check_dims(const rom_dims *d) {
@@ -41,6 +91,14 @@ int check_weights(const rom_dims *d, const rom_weights *w) {
   return ROM_OK;
 }
 
+// slices of the x projection's inner dimension for a launch over `rows` rows
+int xproj_slices_for(const rom_dims *d, int64_t rows) {
+  const bool routed_xdt = d->n_experts_xdt > 1;
+  int n = xproj_k_splits(rows, routed_xdt ? d->n_experts : 1, d->d_inner);
+  const int64_t per = ceil_div(ceil_div(d->d_inner, n), 64) * 64;   // whole 64-wide slabs
+  return static_cast<int>(ceil_div(d->d_inner, per));
+}
+
 Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   const int64_t n_tok = n_seq * seq_len;
   Plan p;
@@ -55,6 +113,12 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   const size_t De = d->d_inner, Dm = d->d_model, R = d->dt_rank;
   const bool multi = K > 1;
   const bool routed_xdt = d->n_experts_xdt > 1;
+  const Segments sg = plan_segments(d, n_seq, seq_len);
+  p.xproj_slices = 1;
+  for (int i = 0; i < sg.n; ++i) {
+    const int n = xproj_slices_for(d, (sg.tok[i + 1] - sg.tok[i]) * (routed_xdt ? d->top_k : 1));
+    if (n > p.xproj_slices) p.xproj_slices = n;
+  }
   p.expert_idx = take(S * 4);
   p.gate = take(S * 4);
   p.counts = take(E * 4);
@@ -67,7 +131,7 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   p.xz = take(N * 2 * De * b);
   p.xz_sorted = multi ? take(S * 2 * De * b) : kNone;
   p.u = take(N * De * b);
-  p.xdbl = take((routed_xdt ? S : N) * (R + 32) * 4 * xproj_k_splits(routed_xdt ? S : N, routed_xdt ? d->n_experts : 1, d->d_inner));
+  p.xdbl = take((routed_xdt ? S : N) * (R + 32) * 4 * p.xproj_slices);
   p.dt_low = take(N * R * b);
   p.bc = take(N * 32 * 4);
   p.dt = take(N * De * b);
@@ -75,31 +139,92 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   p.g = take(N * De * b);
   p.op_sorted = multi ? take(S * Dm * b) : kNone;
   p.conv_tmp = take(static_cast<size_t>(n_seq) * De * 3 * 4);
-  p.scan_q = take(scan_chunk_state_bytes(n_seq, seq_len, d->d_inner));
-  p.scan_p = take(scan_chunk_state_bytes(n_seq, seq_len, d->d_inner));
+  p.seg_lo = take(kMaxSegments * E * 4);
+  p.seg_hi = take(kMaxSegments * E * 4);
+  const bool carry = sg.n > 1 && sg.by_time;
+  p.conv_carry = carry ? take(2 * De * 3 * 4) : kNone;
+  p.ssm_carry = carry ? take(2 * De * 16 * 4) : kNone;
+  for (int i = 0; i < kMaxSegments; ++i) {
+    size_t bytes = 0;
+    if (i < sg.n)
+      bytes = scan_chunk_state_bytes(sg.by_time ? 1 : sg.seq[i + 1] - sg.seq[i],
+                                     sg.by_time ? sg.tok[i + 1] - sg.tok[i] : seq_len, d->d_inner);
+    p.scan_q[i] = take(bytes);
+    p.scan_p[i] = take(bytes);
+  }
   p.total = off;
   return p;
 }
 
+// ---------------------------------------------------------------- second stream of the pipeline
+// One helper stream and a few events per device, created on first use and kept for the life of
+// the process.  Calls on one device share them: calls that overlap on one device from several
+// host threads race on these events.
+struct Side {
+  bool ready = false;
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr, conv_done[kMaxSegments] = {}, dt_done[kMaxSegments] = {},
+             scan_done[kMaxSegments] = {};
+};
+constexpr int kMaxDevices = 32;
+Side g_side[kMaxDevices];
+
+Side *side_for_current_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  Side &sd = g_side[dev];
+  if (!sd.ready) {
+    if (hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+    hipEvent_t *evs[2] = {&sd.fork, &sd.join};
+    for (hipEvent_t *e : evs)
+      if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return nullptr;
+    for (int i = 0; i < kMaxSegments; ++i)
+      if (hipEventCreateWithFlags(&sd.conv_done[i], hipEventDisableTiming) != hipSuccess ||
+          hipEventCreateWithFlags(&sd.dt_done[i], hipEventDisableTiming) != hipSuccess ||
+          hipEventCreateWithFlags(&sd.scan_done[i], hipEventDisableTiming) != hipSuccess)
+        return nullptr;
+    sd.ready = true;
+  }
+  return &sd;
+}
+
 // ---------------------------------------------------------------- stage timing
+// A (begin, end) event pair per call, segment and stage, each recorded on the stream the stage is
+// launched on; begin is recorded after the stage's cross-stream waits.  An uncut call runs its
+// stages back to back on one stream, so there a stage's begin is simply the end of the stage
+// before it (half the events in the timed region).
+constexpr int kProfSlots = kMaxSegments * ROM_STAGE_COUNT * 2;
 struct Profiler {
   int max_calls = 0, n_calls = 0;
-  hipEvent_t *ev = nullptr;          // [max_calls][ROM_STAGE_COUNT + 1]
+  hipEvent_t *ev = nullptr;          // [max_calls][kMaxSegments][ROM_STAGE_COUNT][2]
+  int *begin_of = nullptr;           // [max_calls][kMaxSegments][ROM_STAGE_COUNT]: event index of the begin, -1 = not recorded
 } g_prof;
 
 struct StageMark {
-  hipStream_t s;
   int call;
-  bool on;
-  explicit StageMark(hipStream_t st) : s(st), call(-1), on(false) {
+  bool on, chained;
+  int last_end;
+  explicit StageMark(bool chain) : call(-1), on(false), chained(chain), last_end(-1) {
     if (g_prof.ev && g_prof.n_calls < g_prof.max_calls) {
       call = g_prof.n_calls++;
       on = true;
-      (void)hipEventRecord(g_prof.ev[call * (ROM_STAGE_COUNT + 1)], s);
     }
   }
-  void done(int stage) {   // stages must be marked in increasing order; skipped ones get zero time
-    if (on) (void)hipEventRecord(g_prof.ev[call * (ROM_STAGE_COUNT + 1) + stage + 1], s);
+  void begin(int seg, int stage, hipStream_t s) {
+    if (!on) return;
+    const int slot = call * kProfSlots + (seg * ROM_STAGE_COUNT + stage) * 2;
+    int &b = g_prof.begin_of[call * (kProfSlots / 2) + seg * ROM_STAGE_COUNT + stage];
+    if (chained && last_end >= 0) {
+      b = last_end;
+    } else {
+      (void)hipEventRecord(g_prof.ev[slot], s);
+      b = slot;
+    }
+  }
+  void end(int seg, int stage, hipStream_t s) {
+    if (!on) return;
+    last_end = call * kProfSlots + (seg * ROM_STAGE_COUNT + stage) * 2 + 1;
+    (void)hipEventRecord(g_prof.ev[last_end], s);
   }
 };
 
@@ -113,16 +238,44 @@ __global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict
   if (i < n) dst[i] = src[i];
 }
 
+struct SegTok {
+  int64_t t[kMaxSegments + 1];
+};
+// seg_lo / seg_hi [segment][expert]: the sorted positions of expert e's slots whose token lies in
+// the segment (tok_of_pos is ascending inside every expert's group)
+__global__ void segment_bounds_kernel(const int32_t *__restrict__ offsets, const int32_t *__restrict__ tok_of_pos,
+                                      int n_experts, int n_seg, SegTok bounds, int32_t *__restrict__ seg_lo,
+                                      int32_t *__restrict__ seg_hi) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_seg * n_experts) return;
+  const int p = i / n_experts, e = i % n_experts;
+  const int g_lo = offsets[e], g_hi = offsets[e + 1];
+  int64_t want[2] = {bounds.t[p], bounds.t[p + 1]};
+  int res[2];
+  for (int k = 0; k < 2; ++k) {
+    int lo = g_lo, hi = g_hi;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (tok_of_pos[mid] < want[k]) lo = mid + 1; else hi = mid;
+    }
+    res[k] = lo;
+  }
+  seg_lo[i] = res[0];
+  seg_hi[i] = res[1];
+}
+
 int route_into(const rom_dims *d, const rom_weights *w, const void *x, int64_t n_tok,
                int32_t *expert_idx, float *gate, int32_t *counts, int32_t *offsets, int32_t *perm,
                int32_t *inv_perm, int32_t *tok_of_pos, int32_t *block_counts, float *logits,
                hipStream_t s, StageMark *mark) {
+  if (mark) mark->begin(0, ROM_STAGE_ROUTE, s);
   ROM_TRY(launch_route_topk(d->dtype, x, w->w_router, w->b_router, n_tok, d->d_model, d->n_experts,
                             d->top_k, d->gate_mode, expert_idx, gate, logits, s));
-  if (mark) mark->done(ROM_STAGE_ROUTE);
+  if (mark) mark->end(0, ROM_STAGE_ROUTE, s);
+  if (mark) mark->begin(0, ROM_STAGE_PERMUTE, s);
   ROM_TRY(launch_permutation(expert_idx, n_tok * d->top_k, d->n_experts, d->top_k, block_counts,
                              counts, offsets, perm, inv_perm, tok_of_pos, s));
-  if (mark) mark->done(ROM_STAGE_PERMUTE);
+  if (mark) mark->end(0, ROM_STAGE_PERMUTE, s);
   return ROM_OK;
 }
 
@@ -141,121 +294,207 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   const int64_t N = B * L;
   Plan p = make_plan(d, B, L);
   if (ws_bytes < p.total) return ROM_E_WORKSPACE;
+  const Segments sg = plan_segments(d, B, L);
+  Side *side = nullptr;
+  if (sg.n > 1) {
+    side = side_for_current_device();
+    if (!side) return ROM_E_HIP;
+  }
 
   char *base = static_cast<char *>(ws);
-  auto at = [&](size_t off) { return static_cast<void *>(base + off); };
+  auto at = [&](size_t off) { return base + off; };
   const int K = d->top_k, E = d->n_experts, De = d->d_inner, Dm = d->d_model, R = d->dt_rank;
   const bool multi = K > 1, routed_xdt = d->n_experts_xdt > 1;
   const int64_t S = N * K;
-  int32_t *idx = static_cast<int32_t *>(at(p.expert_idx));
-  float *gate = static_cast<float *>(at(p.gate));
-  int32_t *offsets = static_cast<int32_t *>(at(p.offsets));
-  int32_t *inv_perm = static_cast<int32_t *>(at(p.inv_perm));
-  int32_t *tok_of_pos = static_cast<int32_t *>(at(p.tok_of_pos));
+  float *gate = reinterpret_cast<float *>(at(p.gate));
+  int32_t *offsets = reinterpret_cast<int32_t *>(at(p.offsets));
+  int32_t *inv_perm = reinterpret_cast<int32_t *>(at(p.inv_perm));
+  int32_t *tok_of_pos = reinterpret_cast<int32_t *>(at(p.tok_of_pos));
+  int32_t *seg_lo = reinterpret_cast<int32_t *>(at(p.seg_lo));
+  int32_t *seg_hi = reinterpret_cast<int32_t *>(at(p.seg_hi));
   const size_t eb = d->dtype == ROM_DTYPE_BF16 ? 2 : 4;
 
-  StageMark mark(s);
-  rc = route_into(d, w, x, N, idx, gate, static_cast<int32_t *>(at(p.counts)), offsets,
-                  static_cast<int32_t *>(at(p.perm)), inv_perm, tok_of_pos,
-                  static_cast<int32_t *>(at(p.block_counts)), static_cast<float *>(at(p.logits)), s, &mark);
+  StageMark mark(sg.n == 1);
+  rc = route_into(d, w, x, N, reinterpret_cast<int32_t *>(at(p.expert_idx)), gate,
+                  reinterpret_cast<int32_t *>(at(p.counts)), offsets, reinterpret_cast<int32_t *>(at(p.perm)),
+                  inv_perm, tok_of_pos, reinterpret_cast<int32_t *>(at(p.block_counts)),
+                  reinterpret_cast<float *>(at(p.logits)), s, &mark);
   if (rc != ROM_OK) return rc;
-
-  // in / gate projection, Eq. (10)/(11): gather token rows, scatter back to token order (K == 1)
-  GemmArgs ga;
-  memset(&ga, 0, sizeof(ga));
-  ga.dtype = d->dtype;
-  ga.A = x; ga.lda = Dm; ga.a_rows = tok_of_pos; ga.a_span = N * Dm;
-  ga.W = w->w_in; ga.offsets = offsets; ga.n_groups = E;
-  ga.M = S; ga.N = 2 * De; ga.K = Dm;
-  ga.C = multi ? at(p.xz_sorted) : at(p.xz); ga.ldc = 2 * De; ga.c_rows = multi ? nullptr : tok_of_pos;
-  ROM_TRY(launch_grouped_gemm(ga, s));
-  if (multi)
-    ROM_TRY(launch_slot_sum(eb == 4, eb == 4, at(p.xz_sorted), 2 * De, at(p.xz), 2 * De, inv_perm, N, K,
-                            2 * De, nullptr, 0, s));
-  mark.done(ROM_STAGE_IN_PROJ);
-
-  // short conv + SiLU, Eq. (2)
-  float *conv_tmp = static_cast<float *>(at(p.conv_tmp));
-  ROM_TRY(launch_conv_silu(d->dtype, at(p.xz), 2 * De, w->conv_w, w->conv_b, conv_in,
-                           conv_out ? conv_tmp : nullptr, at(p.u), B, L, De, s));
-  if (conv_out) {
-    const int64_t n = B * De * 3;
-    hipLaunchKernelGGL(copy_f32_kernel, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, s,
-                       conv_tmp, conv_out, n);
+  if (sg.n > 1) {
+    SegTok st;
+    for (int i = 0; i <= kMaxSegments; ++i) st.t[i] = sg.tok[i <= sg.n ? i : sg.n];
+    hipLaunchKernelGGL(segment_bounds_kernel, dim3(static_cast<unsigned>(ceil_div(sg.n * E, 64))), dim3(64), 0, s,
+                       offsets, tok_of_pos, E, sg.n, st, seg_lo, seg_hi);
     ROM_TRY(hipGetLastError());
+    ROM_TRY(hipEventRecord(side->fork, s));
+    ROM_TRY(hipStreamWaitEvent(side->stream, side->fork, 0));
   }
-  mark.done(ROM_STAGE_CONV);
 
-  // x projection -> dt_low | B | C
-  memset(&ga, 0, sizeof(ga));
-  ga.dtype = d->dtype;
-  ga.A = at(p.u); ga.lda = De; ga.a_span = N * De;
-  ga.W = w->w_x; ga.N = R + 32; ga.K = De;
-  ga.C = at(p.xdbl); ga.ldc = R + 32; ga.c_is_f32 = 1;
-  const int64_t x_rows = routed_xdt ? S : N;
-  ga.k_splits = xproj_k_splits(x_rows, routed_xdt ? E : 1, De);
-  {   // the slice length is rounded up to whole 64-wide slabs: use the slice count that results
-    const int64_t per = ceil_div(ceil_div(De, ga.k_splits), 64) * 64;
-    ga.k_splits = static_cast<int>(ceil_div(De, per));
-  }
-  ga.c_split_stride = x_rows * (R + 32);
-  if (routed_xdt) {
-    ga.a_rows = tok_of_pos; ga.offsets = offsets; ga.n_groups = E; ga.M = S;
-    ga.c_rows = multi ? nullptr : tok_of_pos;
-  } else {
-    ga.n_groups = 1; ga.M = N;
-  }
-  ROM_TRY(launch_grouped_gemm(ga, s));
-  ROM_TRY(launch_split_xdbl(d->dtype, static_cast<const float *>(at(p.xdbl)), ga.k_splits, ga.c_split_stride,
-                            (routed_xdt && multi) ? inv_perm : nullptr, K, N, R, at(p.dt_low),
-                            static_cast<float *>(at(p.bc)), s));
-  mark.done(ROM_STAGE_X_PROJ);
+  for (int sgi = 0; sgi < sg.n; ++sgi) {
+    hipStream_t st = (sgi & 1) ? side->stream : s;
+    const int64_t tok0 = sg.tok[sgi], n_tok = sg.tok[sgi + 1] - sg.tok[sgi];
+    const int64_t n_slots = n_tok * K;
+    const int64_t seq0 = sg.by_time ? 0 : sg.seq[sgi];
+    const int64_t n_seq = sg.by_time ? 1 : sg.seq[sgi + 1] - sg.seq[sgi];
+    const int64_t seq_len = sg.by_time ? n_tok : L;
+    const bool first = sgi == 0, last = sgi == sg.n - 1;
+    // the routed GEMMs of a segment: expert e's rows are the sorted positions [lo[e], hi[e])
+    auto routed = [&](GemmArgs &ga) {
+      ga.n_groups = E;
+      ga.M = n_slots;
+      if (sg.n > 1) {
+        ga.offsets = seg_lo + sgi * E;
+        ga.offsets_hi = seg_hi + sgi * E;
+      } else {
+        ga.offsets = offsets;
+      }
+    };
+    // stagger: start this segment's GEMMs beside the previous segment's scan
+    if (!first && kStagger == 2) ROM_TRY(hipStreamWaitEvent(st, side->dt_done[sgi - 1], 0));
+    if (!first && kStagger == 1) ROM_TRY(hipStreamWaitEvent(st, side->conv_done[sgi - 1], 0));
 
-  // dt projection + bias + softplus
-  memset(&ga, 0, sizeof(ga));
-  ga.dtype = d->dtype;
-  ga.A = at(p.dt_low); ga.lda = R; ga.a_span = N * R;
-  ga.W = w->w_dt; ga.N = De; ga.K = R;
-  if (routed_xdt && multi) {
-    ga.a_rows = tok_of_pos; ga.offsets = offsets; ga.n_groups = E; ga.M = S;
-    ga.C = at(p.dt_raw); ga.ldc = De; ga.c_is_f32 = 1;
-    ROM_TRY(launch_grouped_gemm(ga, s));
-    ROM_TRY(launch_slot_sum(1, eb == 4, at(p.dt_raw), De, at(p.dt), De, inv_perm, N, K, De, w->dt_bias, 1, s));
-  } else {
-    if (routed_xdt) {
-      ga.a_rows = tok_of_pos; ga.offsets = offsets; ga.n_groups = E; ga.M = S; ga.c_rows = tok_of_pos;
-    } else {
-      ga.n_groups = 1; ga.M = N;
+    // in / gate projection, Eq. (10)/(11): gather token rows, scatter back to token order (K == 1)
+    mark.begin(sgi, ROM_STAGE_IN_PROJ, st);
+    GemmArgs ga;
+    memset(&ga, 0, sizeof(ga));
+    ga.dtype = d->dtype;
+    ga.A = x; ga.lda = Dm; ga.a_rows = tok_of_pos; ga.a_span = N * Dm;
+    ga.W = w->w_in; ga.N = 2 * De; ga.K = Dm;
+    routed(ga);
+    ga.C = multi ? at(p.xz_sorted) : at(p.xz); ga.ldc = 2 * De; ga.c_rows = multi ? nullptr : tok_of_pos;
+    ROM_TRY(launch_grouped_gemm(ga, st));
+    if (multi)
+      ROM_TRY(launch_slot_sum(eb == 4, eb == 4, at(p.xz_sorted), 2 * De, at(p.xz) + tok0 * 2 * De * eb, 2 * De,
+                              inv_perm + tok0 * K, n_tok, K, 2 * De, nullptr, 0, st));
+    mark.end(sgi, ROM_STAGE_IN_PROJ, st);
+
+    // short conv + SiLU, Eq. (2).  A time segment takes the three rows before it from the
+    // previous segment's end state (that conv ran before the dt projection waited for above).
+    if (!first && sg.by_time) ROM_TRY(hipStreamWaitEvent(st, side->conv_done[sgi - 1], 0));
+    mark.begin(sgi, ROM_STAGE_CONV, st);
+    {
+      const float *cin = conv_in ? conv_in + seq0 * De * 3 : nullptr;
+      float *cout_final = conv_out ? conv_out + seq0 * De * 3 : nullptr;
+      float *ctmp = reinterpret_cast<float *>(at(p.conv_tmp)) + seq0 * De * 3;
+      float *cdst = cout_final ? ctmp : nullptr;       // conv_out may alias conv_in: write beside, then copy
+      if (sg.by_time && sg.n > 1) {
+        float *carry = reinterpret_cast<float *>(at(p.conv_carry));
+        if (!first) cin = carry + ((sgi - 1) & 1) * De * 3;
+        if (!last) { cdst = carry + (sgi & 1) * De * 3; cout_final = nullptr; }
+      }
+      ROM_TRY(launch_conv_silu(d->dtype, at(p.xz) + tok0 * 2 * De * eb, 2 * De, w->conv_w, w->conv_b, cin, cdst,
+                               at(p.u) + tok0 * De * eb, n_seq, seq_len, De, st));
+      if (cout_final) {
+        const int64_t n = n_seq * De * 3;
+        hipLaunchKernelGGL(copy_f32_kernel, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, st,
+                           ctmp, cout_final, n);
+        ROM_TRY(hipGetLastError());
+      }
     }
-    ga.C = at(p.dt); ga.ldc = De; ga.bias = w->dt_bias; ga.softplus = 1;
-    ROM_TRY(launch_grouped_gemm(ga, s));
+    mark.end(sgi, ROM_STAGE_CONV, st);
+    if (sg.n > 1) ROM_TRY(hipEventRecord(side->conv_done[sgi], st));
+
+    // x projection -> dt_low | B | C
+    mark.begin(sgi, ROM_STAGE_X_PROJ, st);
+    memset(&ga, 0, sizeof(ga));
+    ga.dtype = d->dtype;
+    ga.lda = De; ga.a_span = N * De;
+    ga.W = w->w_x; ga.N = R + 32; ga.K = De;
+    ga.ldc = R + 32; ga.c_is_f32 = 1;
+    ga.k_splits = xproj_slices_for(d, routed_xdt ? n_slots : n_tok);
+    if (ga.k_splits > p.xproj_slices) ga.k_splits = p.xproj_slices;
+    ga.c_split_stride = (routed_xdt ? S : N) * (R + 32);
+    float *xdbl = reinterpret_cast<float *>(at(p.xdbl));
+    if (routed_xdt) {
+      ga.A = at(p.u); ga.a_rows = tok_of_pos; ga.C = xdbl;
+      routed(ga);
+      ga.c_rows = multi ? nullptr : tok_of_pos;
+    } else {
+      ga.A = at(p.u) + tok0 * De * eb; ga.a_span = n_tok * De; ga.C = xdbl + tok0 * (R + 32);
+      ga.n_groups = 1; ga.M = n_tok;
+    }
+    ROM_TRY(launch_grouped_gemm(ga, st));
+    {
+      const bool by_pos = routed_xdt && multi;      // xdbl rows in sorted-slot order, else in token order
+      ROM_TRY(launch_split_xdbl(d->dtype, by_pos ? xdbl : xdbl + tok0 * (R + 32), ga.k_splits, ga.c_split_stride,
+                                by_pos ? inv_perm + tok0 * K : nullptr, K, n_tok, R, at(p.dt_low) + tok0 * R * eb,
+                                reinterpret_cast<float *>(at(p.bc)) + tok0 * 32, st));
+    }
+    mark.end(sgi, ROM_STAGE_X_PROJ, st);
+
+    // dt projection + bias + softplus
+    mark.begin(sgi, ROM_STAGE_DT_PROJ, st);
+    memset(&ga, 0, sizeof(ga));
+    ga.dtype = d->dtype;
+    ga.lda = R; ga.a_span = N * R;
+    ga.W = w->w_dt; ga.N = De; ga.K = R; ga.ldc = De;
+    if (routed_xdt && multi) {
+      ga.A = at(p.dt_low); ga.a_rows = tok_of_pos;
+      routed(ga);
+      ga.C = at(p.dt_raw); ga.c_is_f32 = 1;
+      ROM_TRY(launch_grouped_gemm(ga, st));
+      ROM_TRY(launch_slot_sum(1, eb == 4, at(p.dt_raw), De, at(p.dt) + tok0 * De * eb, De, inv_perm + tok0 * K,
+                              n_tok, K, De, w->dt_bias, 1, st));
+    } else {
+      if (routed_xdt) {
+        ga.A = at(p.dt_low); ga.a_rows = tok_of_pos; ga.C = at(p.dt); ga.c_rows = tok_of_pos;
+        routed(ga);
+      } else {
+        ga.A = at(p.dt_low) + tok0 * R * eb; ga.a_span = n_tok * R; ga.C = at(p.dt) + tok0 * De * eb;
+        ga.n_groups = 1; ga.M = n_tok;
+      }
+      ga.bias = w->dt_bias; ga.softplus = 1;
+      ROM_TRY(launch_grouped_gemm(ga, st));
+    }
+    mark.end(sgi, ROM_STAGE_DT_PROJ, st);
+    if (sg.n > 1) ROM_TRY(hipEventRecord(side->dt_done[sgi], st));
+
+    // selective scan + D skip + SiLU(z) gate, Eq. (5), (6); a time segment starts from the state
+    // the previous one ended in
+    if (!first && sg.by_time) ROM_TRY(hipStreamWaitEvent(st, side->scan_done[sgi - 1], 0));
+    mark.begin(sgi, ROM_STAGE_SCAN, st);
+    {
+      const float *hin = ssm_in ? ssm_in + seq0 * De * 16 : nullptr;
+      float *hout = ssm_out ? ssm_out + seq0 * De * 16 : nullptr;
+      if (sg.by_time && sg.n > 1) {
+        float *carry = reinterpret_cast<float *>(at(p.ssm_carry));
+        if (!first) hin = carry + ((sgi - 1) & 1) * De * 16;
+        if (!last) hout = carry + (sgi & 1) * De * 16;
+      }
+      const char *z = at(p.xz) + static_cast<size_t>(De) * eb + tok0 * 2 * De * eb;
+      ROM_TRY(launch_scan_gate(d->dtype, at(p.u) + tok0 * De * eb, at(p.dt) + tok0 * De * eb,
+                               reinterpret_cast<const float *>(at(p.bc)) + tok0 * 32, z, 2 * De, w->A_log, w->D, hin,
+                               hout, at(p.g) + tok0 * De * eb, n_seq, seq_len, De,
+                               reinterpret_cast<float *>(at(p.scan_q[sgi])), reinterpret_cast<float *>(at(p.scan_p[sgi])),
+                               st));
+    }
+    mark.end(sgi, ROM_STAGE_SCAN, st);
+    if (sg.n > 1) ROM_TRY(hipEventRecord(side->scan_done[sgi], st));
+
+    // out projection, Eq. (13), and the gate-weighted combine, Eq. (12)
+    mark.begin(sgi, ROM_STAGE_OUT_PROJ, st);
+    memset(&ga, 0, sizeof(ga));
+    ga.dtype = d->dtype;
+    ga.A = at(p.g); ga.lda = De; ga.a_rows = tok_of_pos; ga.a_span = N * De;
+    ga.W = w->w_out; ga.N = Dm; ga.K = De;
+    routed(ga);
+    if (multi) {
+      ga.C = at(p.op_sorted); ga.ldc = Dm;
+      ROM_TRY(launch_grouped_gemm(ga, st));
+      mark.end(sgi, ROM_STAGE_OUT_PROJ, st);
+      mark.begin(sgi, ROM_STAGE_COMBINE, st);
+      ROM_TRY(launch_combine(d->dtype, at(p.op_sorted), inv_perm + tok0 * K, gate + tok0 * K,
+                             static_cast<char *>(out) + tok0 * Dm * eb, n_tok, K, Dm, st));
+      mark.end(sgi, ROM_STAGE_COMBINE, st);
+    } else {
+      ga.C = out; ga.ldc = Dm; ga.c_rows = tok_of_pos; ga.row_scale = gate;   // gate[n*1 + 0]
+      ROM_TRY(launch_grouped_gemm(ga, st));
+      mark.end(sgi, ROM_STAGE_OUT_PROJ, st);
+    }
   }
-  mark.done(ROM_STAGE_DT_PROJ);
-
-  // selective scan + D skip + SiLU(z) gate, Eq. (5), (6)
-  const char *z = static_cast<const char *>(at(p.xz)) + static_cast<size_t>(De) * eb;
-  ROM_TRY(launch_scan_gate(d->dtype, at(p.u), at(p.dt), static_cast<const float *>(at(p.bc)), z, 2 * De,
-                           w->A_log, w->D, ssm_in, ssm_out, at(p.g), B, L, De,
-                           static_cast<float *>(at(p.scan_q)), static_cast<float *>(at(p.scan_p)), s));
-  mark.done(ROM_STAGE_SCAN);
-
-  // out projection, Eq. (13), and the gate-weighted combine, Eq. (12)
-  memset(&ga, 0, sizeof(ga));
-  ga.dtype = d->dtype;
-  ga.A = at(p.g); ga.lda = De; ga.a_rows = tok_of_pos; ga.a_span = N * De;
-  ga.W = w->w_out; ga.offsets = offsets; ga.n_groups = E;
-  ga.M = S; ga.N = Dm; ga.K = De;
-  if (multi) {
-    ga.C = at(p.op_sorted); ga.ldc = Dm;
-    ROM_TRY(launch_grouped_gemm(ga, s));
-    mark.done(ROM_STAGE_OUT_PROJ);
-    ROM_TRY(launch_combine(d->dtype, at(p.op_sorted), inv_perm, gate, out, N, K, Dm, s));
-    mark.done(ROM_STAGE_COMBINE);
-  } else {
-    ga.C = out; ga.ldc = Dm; ga.c_rows = tok_of_pos; ga.row_scale = gate;   // gate[n*1 + 0]
-    ROM_TRY(launch_grouped_gemm(ga, s));
-    mark.done(ROM_STAGE_OUT_PROJ);
-    mark.done(ROM_STAGE_COMBINE);
+  if (sg.n > 1) {   // the caller's stream continues when both are done
+    ROM_TRY(hipEventRecord(side->join, side->stream));
+    ROM_TRY(hipStreamWaitEvent(s, side->join, 0));
   }
   return ROM_OK;
 }
@@ -343,15 +582,19 @@ const char *rom_strerror(int code) {
 
 int rom_profile_enable(int max_calls) {
   if (g_prof.ev) {
-    for (int i = 0; i < g_prof.max_calls * (ROM_STAGE_COUNT + 1); ++i) (void)hipEventDestroy(g_prof.ev[i]);
+    for (int i = 0; i < g_prof.max_calls * kProfSlots; ++i) (void)hipEventDestroy(g_prof.ev[i]);
     delete[] g_prof.ev;
+    delete[] g_prof.begin_of;
     g_prof.ev = nullptr;
+    g_prof.begin_of = nullptr;
   }
   g_prof.max_calls = 0;
   g_prof.n_calls = 0;
   if (max_calls <= 0) return ROM_OK;
-  const int n = max_calls * (ROM_STAGE_COUNT + 1);
+  const int n = max_calls * kProfSlots;
   g_prof.ev = new hipEvent_t[n];
+  g_prof.begin_of = new int[n / 2];
+  for (int i = 0; i < n / 2; ++i) g_prof.begin_of[i] = -1;
   for (int i = 0; i < n; ++i)
     if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) return ROM_E_HIP;
   g_prof.max_calls = max_calls;
@@ -363,15 +606,24 @@ int rom_profile_collect(double *stage_ms, int *n_calls) {
   for (int i = 0; i < ROM_STAGE_COUNT; ++i) stage_ms[i] = 0.0;
   *n_calls = g_prof.n_calls;
   for (int c = 0; c < g_prof.n_calls; ++c) {
-    hipEvent_t *ev = g_prof.ev + c * (ROM_STAGE_COUNT + 1);
-    if (hipEventSynchronize(ev[ROM_STAGE_COUNT]) != hipSuccess) return ROM_E_HIP;
-    for (int i = 0; i < ROM_STAGE_COUNT; ++i) {
+    for (int i = 0; i < kProfSlots / 2; ++i) {
+      int &b = g_prof.begin_of[c * (kProfSlots / 2) + i];
+      if (b < 0) continue;
+      hipEvent_t end = g_prof.ev[c * kProfSlots + i * 2 + 1];
+      if (hipEventSynchronize(end) != hipSuccess) return ROM_E_HIP;
       float ms = 0.0f;
-      if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess) return ROM_E_HIP;
-      stage_ms[i] += ms;
+      if (hipEventElapsedTime(&ms, g_prof.ev[b], end) != hipSuccess) return ROM_E_HIP;
+      stage_ms[i % ROM_STAGE_COUNT] += ms;
+      b = -1;
     }
   }
   g_prof.n_calls = 0;
+  return ROM_OK;
+}
+
+int rom_set_segments(int n_segments) {
+  if (n_segments < 0 || n_segments > kMaxSegments) return ROM_E_INVAL;
+  g_force_segments = n_segments;
   return ROM_OK;
 }
 

@@ -76,7 +76,7 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmArgs &a, int BM, int 
   } else {
     int rem = mt;
     for (int e = 0; e < a.n_groups; ++e) {
-      const int lo = a.offsets[e], hi = a.offsets[e + 1];
+      const int lo = a.offsets[e], hi = a.offsets_hi ? a.offsets_hi[e] : a.offsets[e + 1];
       const int tiles = (hi - lo + BM - 1) / BM;
       if (rem < tiles) {
         tc.group = e;
@@ -141,12 +141,17 @@ __device__ __forceinline__ void mfma_epilogue(const GemmArgs &a, const TileCoord
       }
     }
   } else {
-    // bf16 output: every wave parks its sub-tile (after bias / softplus / row scale) in its own
-    // slice of the now idle LDS, then writes it out row by row, 16 bytes per lane, so that each
-    // store instruction covers whole 128..256-byte row segments.  No workgroup barrier is needed:
-    // after the last slab's barrier nobody reads the operand buffers for real any more.
+    // bf16 output: every wave parks 32 rows of its sub-tile at a time (after bias / softplus / row
+    // scale) in its own slice of the now idle LDS, then writes them out row by row, 16 bytes per
+    // lane, so that each store instruction covers whole 128..256-byte row segments.  No workgroup
+    // barrier is needed: after the last slab's barrier nobody reads the operand buffers for real
+    // any more, and LDS serves one wave's accesses in program order.
     constexpr int kPitch = WTN * 2 + 16;                 // bytes per parked row (16-byte aligned)
-    char *stage = reinterpret_cast<char *>(smem) + wave * (WTM * kPitch);
+    char *stage = reinterpret_cast<char *>(smem) + wave * (32 * kPitch);
+    constexpr int kChunks = WTN / 8;                     // 16-byte chunks per parked row
+    constexpr int kRowsPerPass = 64 / kChunks;
+    const int chunk = lane % kChunks, sub = lane / kChunks;
+    const int col = tc.n0 + wn * WTN + chunk * 8;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       float scale = 1.0f;
@@ -163,9 +168,9 @@ __device__ __forceinline__ void mfma_epilogue(const GemmArgs &a, const TileCoord
 #pragma unroll
           for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
           if (EPI == kEpiBiasSoftplus) {
-            const int col = tc.n0 + wn * WTN + lcol;
+            const int bcol = tc.n0 + wn * WTN + lcol;
             float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (col < a.N) b4 = *reinterpret_cast<const float4 *>(a.bias + col);
+            if (bcol < a.N) b4 = *reinterpret_cast<const float4 *>(a.bias + bcol);
             v[0] = softplus_fast(v[0] + b4.x); v[1] = softplus_fast(v[1] + b4.y);
             v[2] = softplus_fast(v[2] + b4.z); v[3] = softplus_fast(v[3] + b4.w);
           }
@@ -176,22 +181,18 @@ __device__ __forceinline__ void mfma_epilogue(const GemmArgs &a, const TileCoord
           uint2 pk;
           pk.x = pack_bf16x2(v[0], v[1]);
           pk.y = pack_bf16x2(v[2], v[3]);
-          *reinterpret_cast<uint2 *>(stage + (i * 32 + frag_row) * kPitch + lcol * 2) = pk;
+          *reinterpret_cast<uint2 *>(stage + frag_row * kPitch + lcol * 2) = pk;
         }
       }
-    }
-    constexpr int kChunks = WTN / 8;                     // 16-byte chunks per parked row
-    constexpr int kRowsPerPass = 64 / kChunks;
-    const int chunk = lane % kChunks, sub = lane / kChunks;
-    const int col = tc.n0 + wn * WTN + chunk * 8;
 #pragma unroll 4
-    for (int r0 = 0; r0 < WTM; r0 += kRowsPerPass) {
-      const int row = r0 + sub;
-      const int64_t p = tc.row0 + wm * WTM + row;
-      if (p < tc.row_end && col < a.N) {
-        const int64_t crow = a.c_rows ? a.c_rows[p] : p;
-        const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * kPitch + chunk * 16);
-        *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.C) + crow * a.ldc + col) = v;
+      for (int r0 = 0; r0 < 32; r0 += kRowsPerPass) {
+        const int row = r0 + sub;
+        const int64_t p = tc.row0 + wm * WTM + i * 32 + row;
+        if (row < 32 && p < tc.row_end && col < a.N) {
+          const int64_t crow = a.c_rows ? a.c_rows[p] : p;
+          const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * kPitch + chunk * 16);
+          *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.C) + crow * a.ldc + col) = v;
+        }
       }
     }
   }
@@ -451,6 +452,7 @@ __device__ __forceinline__ void dma_load_16(unsigned lds_addr, unsigned voff, co
 template <int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a) {
   constexpr int BM = 256;
+  static_assert(kDmaSlots == 4 || kDmaSlots == 5, "ring of four or five half-slab slots");
   static_assert(WM * WN == 8 && BN <= BM && BN % (32 * WN) == 0, "eight waves, 32-wide MFMA tiles");
   constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
   constexpr int kSlotChunks = BM * kDmaRC;                    // 16-byte chunks per ring slot
@@ -551,7 +553,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a) {
 #pragma unroll
   for (int h = 0; h < kDmaSlots; ++h) issue(h);
   // slab 0 is in LDS once only A(1), W(1), A(2) are outstanding
-  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * kAInstr + kWInstr) : "memory");
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kDmaSlots == 5 ? 2 * kAInstr + kWInstr : kAInstr + kWInstr) : "memory");
   load_frags(0, 0, fa0, fb0);
 
   for (int m = 0; m < KT; ++m) {
@@ -562,7 +564,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a) {
     load_frags(m, 3, fa1, fb1);
     mma(fa0, fb0);
     // slab m+1 has landed for everyone (only A(m+2) is outstanding) and nobody reads slab m any more
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kAInstr) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kDmaSlots == 5 ? kAInstr : 0) : "memory");
     issue(2 * m + kDmaSlots);                                            // W(m+2) into the slot of A(m)
     issue(2 * m + kDmaSlots + 1);                                        // A(m+3) into the slot of W(m)
     load_frags(m + 1, 0, fa0, fb0);
@@ -741,7 +743,7 @@ int grid_tiles(const GemmArgs &a, int BM, int BN) {
 template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL>
 hipError_t launch_mfma_k(const GemmArgs &a, hipStream_t s) {
   constexpr int kLoopSmem = 2 * (BM + BN) * kRowChunks * 16;
-  constexpr int kStageSmem = EPI == kEpiPlainF32 ? 0 : BM * WN * ((BN / WN) * 2 + 16);
+  constexpr int kStageSmem = EPI == kEpiPlainF32 ? 0 : WM * WN * 32 * ((BN / WN) * 2 + 16);
   constexpr int kSmem = kLoopSmem > kStageSmem ? kLoopSmem : kStageSmem;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {

@@ -58,7 +58,8 @@ struct GemmArgs {
   const int32_t *a_rows;     // row of A for position p, NULL = p
   int64_t a_span;            // number of elements of A that may be addressed (rows * lda)
   const void *W;             // [n_groups, N, K] row-major
-  const int32_t *offsets;    // NULL = single group
+  const int32_t *offsets;    // NULL = single group; group e is the rows [offsets[e], offsets[e + 1]) ...
+  const int32_t *offsets_hi; // ... or, if not NULL, [offsets[e], offsets_hi[e]) (device, i32 [n_groups])
   int n_groups;
   int64_t M;                 // total rows (positions)
   int N, K;                  // out features, in features

@@ -67,6 +67,45 @@ def test_medium_layers_big_tile_kernels(kw):
     compare_layer(cfg, gpu, x, w)
 
 
+@pytest.mark.parametrize("n_seg", [2, 3, 4])
+@pytest.mark.parametrize("kw", [
+    dict(batch=1, seq_len=301),                                # one sequence cut in time: conv / scan carry
+    dict(batch=1, seq_len=150, top_k=2, gate_mode=1),
+    dict(batch=3, seq_len=97),                                 # whole sequences dealt to segments
+    dict(batch=5, seq_len=40, top_k=2, gate_mode=0, dtype="fp32"),
+    dict(batch=1, seq_len=200, routed_xdt=False),
+    dict(batch=1, seq_len=130, n_experts=64, top_k=8, gate_mode=1),   # most experts empty in a segment
+])
+def test_segmented_pipeline(kw, n_seg):
+    """The two-stream software pipeline (forced here; automatic only for long calls) against the
+    oracle, with incoming and outgoing states."""
+    from paper_2506_18145_amd import rom_set_segments
+    cfg = small_cfg(**kw)
+    cs, ss = make_states(cfg)
+    rom_set_segments(n_seg)
+    try:
+        _, gpu, x, w = run_layer(cfg, cs, ss)
+    finally:
+        rom_set_segments(0)
+    compare_layer(cfg, gpu, x, w, cs, ss)
+
+
+def test_segmented_pipeline_is_deterministic_and_matches_unsegmented_routing():
+    from paper_2506_18145_amd import rom_set_segments
+    cfg = small_cfg(batch=1, seq_len=1000, d_model=128, d_inner=256, dt_rank=8, n_experts=8)
+    _, base, x, w = run_layer(cfg)
+    rom_set_segments(3)
+    try:
+        _, seg1, _, _ = run_layer(cfg)
+        _, seg2, _, _ = run_layer(cfg)
+    finally:
+        rom_set_segments(0)
+    for name in ("expert_idx", "counts", "offsets", "perm", "inv_perm"):
+        assert np.array_equal(base[name], seg1[name])
+    assert np.array_equal(seg1["out"], seg2["out"])
+    assert rel_err(seg1["out"], base["out"]) <= TOL["bf16"] * 0.25
+
+
 def test_carried_state_and_split_sequence():
     cfg = small_cfg(seq_len=150, top_k=2, gate_mode=1)
     cs, ss = make_states(cfg)
