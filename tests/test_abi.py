@@ -111,3 +111,29 @@ def test_binding_refuses_to_run_without_a_gpu():
     cfg = get_config("cfg0")
     with pytest.raises(RomError):
         RomLayer(cfg, make_weights(cfg))
+
+
+def test_segment_knob_is_validated_and_keeps_the_workspace_plan_consistent(lib):
+    from paper_2506_18145_amd import binding
+    d = _dims(dtype=1, d_model=256, d_inner=512, dt_rank=16)
+    base = binding.rom_workspace_bytes(d, 1, 1000)
+    try:
+        binding.rom_set_segments(1)
+        assert binding.rom_workspace_bytes(d, 1, 1000) == base          # 0 and 1: never cut
+        binding.rom_set_segments(3)
+        cut = binding.rom_workspace_bytes(d, 1, 1000)
+        assert cut > 0
+        binding.rom_set_segments(0)
+        steps = binding.rom_workspace_bytes(d, 4, 1)
+        binding.rom_set_segments(3)
+        assert binding.rom_workspace_bytes(d, 4, 1) == steps                # single steps are never cut
+        lay = binding.rom_workspace_layout(d, 1, 1000)
+        assert lay["total_bytes"] == cut
+        with pytest.raises(binding.RomError):
+            binding.rom_set_segments(5)
+        with pytest.raises(binding.RomError):
+            binding.rom_set_segments(-1)
+    finally:
+        binding.rom_set_segments(0)
+    assert binding.rom_workspace_bytes(d, 1, 1000) == base
+
