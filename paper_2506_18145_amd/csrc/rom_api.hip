@@ -376,7 +376,11 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
       const float *cin = conv_in ? conv_in + seq0 * De * 3 : nullptr;
       float *cout_final = conv_out ? conv_out + seq0 * De * 3 : nullptr;
       float *ctmp = reinterpret_cast<float *>(at(p.conv_tmp)) + seq0 * De * 3;
-      float *cdst = cout_final ? ctmp : nullptr;       // conv_out may alias conv_in: write beside, then copy
+      // conv_out may alias conv_in (rom_step): a sequence of up to 32 steps is one run of one
+      // thread, which reads the old state before it writes the new one; longer sequences are cut
+      // into runs for different blocks, so the new state goes beside the old one and is copied over
+      float *cdst = cout_final ? ctmp : nullptr;
+      if (cout_final && seq_len <= 32) { cdst = cout_final; cout_final = nullptr; }
       if (sg.by_time && sg.n > 1) {
         float *carry = reinterpret_cast<float *>(at(p.conv_carry));
         if (!first) cin = carry + ((sgi - 1) & 1) * De * 3;

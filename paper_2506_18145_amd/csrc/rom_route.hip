@@ -38,18 +38,24 @@ template <> struct Vec8<float> {
   __device__ __forceinline__ float get(int i) const { return i < 4 ? (&lo.x)[i] : (&hi.x)[i - 4]; }
 };
 
-// One wavefront handles TOK consecutive tokens: lanes stride over d_model in chunks of 8,
-// each lane keeps TOK x EMAX partial dot products, a fixed butterfly sums them.
+// WPT wavefronts handle TOK consecutive tokens: lanes stride over d_model in chunks of 8, each
+// lane keeps TOK x EMAX partial dot products, a fixed butterfly sums them (and, for WPT = 4, the
+// four waves of the block hand their sums to wave 0 through LDS, added in wave order).
 // Lane e then owns logit e of each token and the wave does K arg-max rounds by ballot.
-template <typename T, int EMAX, int TOK>
+// WPT = 4 is for launches with few tokens (the recurrent step): one token per wave would leave
+// most of the chip idle behind a long chain of dependent loads.
+template <typename T, int EMAX, int TOK, int WPT>
 __global__ __launch_bounds__(256) void route_topk_kernel(
     const T *__restrict__ x, const T *__restrict__ w_router, const float *__restrict__ b_router,
     int64_t n_tokens, int d_model, int n_experts, int top_k, int gate_mode,
     int32_t *__restrict__ expert_idx, float *__restrict__ gate, float *__restrict__ logits) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const int64_t wave_id = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / kWave;
-  const int64_t tok0 = wave_id * TOK;
-  if (tok0 >= n_tokens) return;
+  static_assert(WPT == 1 || WPT == 4, "one wave or one block per token group");
+  __shared__ float part[WPT == 4 ? 4 * TOK * EMAX : 1];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int64_t group_id = WPT == 4 ? static_cast<int64_t>(blockIdx.x)
+                                    : (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / kWave;
+  const int64_t tok0 = group_id * TOK;
+  if (tok0 >= n_tokens) return;          // whole block (WPT = 4) or whole wave
 
   float acc[TOK][EMAX];
 #pragma unroll
@@ -57,7 +63,8 @@ __global__ __launch_bounds__(256) void route_topk_kernel(
 #pragma unroll
     for (int e = 0; e < EMAX; ++e) acc[t][e] = 0.0f;
 
-  for (int d0 = lane * 8; d0 < d_model; d0 += kWave * 8) {
+  const int first = (WPT == 4 ? wave * kWave + lane : lane) * 8;
+  for (int d0 = first; d0 < d_model; d0 += WPT * kWave * 8) {
     Vec8<T> xv[TOK];
 #pragma unroll
     for (int t = 0; t < TOK; ++t) {
@@ -79,15 +86,36 @@ __global__ __launch_bounds__(256) void route_topk_kernel(
     }
   }
 
+  if (WPT == 4) {
+#pragma unroll
+    for (int t = 0; t < TOK; ++t)
+#pragma unroll
+      for (int e = 0; e < EMAX; ++e) {
+        const float s = wave_sum(acc[t][e]);
+        if (lane == 0) part[(wave * TOK + t) * EMAX + e] = s;
+      }
+    __syncthreads();
+    if (wave != 0) return;
+  }
+
 #pragma unroll
   for (int t = 0; t < TOK; ++t) {
     const int64_t tok = tok0 + t;
     // lane e keeps logit e
     float mine = -INFINITY;
+    if (WPT == 4) {
+      if (lane < n_experts && lane < EMAX) {
+        float s = part[t * EMAX + lane];
 #pragma unroll
-    for (int e = 0; e < EMAX; ++e) {
-      const float s = wave_sum(acc[t][e]);
-      if (lane == e && e < n_experts) mine = s + (b_router ? b_router[e] : 0.0f);
+        for (int w = 1; w < 4; ++w) s += part[(w * TOK + t) * EMAX + lane];
+        mine = s + (b_router ? b_router[lane] : 0.0f);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < EMAX; ++e) {
+        const float s = wave_sum(acc[t][e]);
+        if (lane == e && e < n_experts) mine = s + (b_router ? b_router[e] : 0.0f);
+      }
     }
     if (tok >= n_tokens) continue;
     if (logits && lane < n_experts) logits[tok * n_experts + lane] = mine;
@@ -260,21 +288,23 @@ hipError_t route_dispatch(const void *x, const void *w_router, const float *b_ro
                           int32_t *expert_idx, float *gate, float *logits, hipStream_t s) {
   const T *xp = static_cast<const T *>(x);
   const T *wp = static_cast<const T *>(w_router);
-#define ROM_ROUTE_LAUNCH(EMAX, TOK)                                                              \
+#define ROM_ROUTE_LAUNCH(EMAX, TOK, WPT)                                                         \
   do {                                                                                           \
-    const int64_t waves = ceil_div(n_tokens, TOK);                                               \
-    const int64_t blocks = ceil_div(waves, 4);                                                   \
-    hipLaunchKernelGGL((route_topk_kernel<T, EMAX, TOK>), dim3(static_cast<unsigned>(blocks)),   \
+    const int64_t groups = ceil_div(n_tokens, TOK);                                              \
+    const int64_t blocks = WPT == 4 ? groups : ceil_div(groups, 4);                              \
+    hipLaunchKernelGGL((route_topk_kernel<T, EMAX, TOK, WPT>), dim3(static_cast<unsigned>(blocks)), \
                        dim3(256), 0, s, xp, wp, b_router, n_tokens, d_model, n_experts, top_k,   \
                        gate_mode, expert_idx, gate, logits);                                     \
   } while (0)
-  // few tokens: one token per wavefront so that the launch still spreads over the chip
-  if (n_tokens <= 8192 && n_experts <= 8) ROM_ROUTE_LAUNCH(8, 1);
-  else if (n_tokens <= 8192 && n_experts <= 16) ROM_ROUTE_LAUNCH(16, 1);
-  else if (n_experts <= 8) ROM_ROUTE_LAUNCH(8, 4);
-  else if (n_experts <= 16) ROM_ROUTE_LAUNCH(16, 2);
-  else if (n_experts <= 32) ROM_ROUTE_LAUNCH(32, 1);
-  else ROM_ROUTE_LAUNCH(64, 1);
+  // few tokens: one token per block / per wavefront so that the launch still spreads over the chip
+  if (n_tokens <= 1024 && n_experts <= 8) ROM_ROUTE_LAUNCH(8, 1, 4);
+  else if (n_tokens <= 1024 && n_experts <= 16) ROM_ROUTE_LAUNCH(16, 1, 4);
+  else if (n_tokens <= 8192 && n_experts <= 8) ROM_ROUTE_LAUNCH(8, 1, 1);
+  else if (n_tokens <= 8192 && n_experts <= 16) ROM_ROUTE_LAUNCH(16, 1, 1);
+  else if (n_experts <= 8) ROM_ROUTE_LAUNCH(8, 4, 1);
+  else if (n_experts <= 16) ROM_ROUTE_LAUNCH(16, 2, 1);
+  else if (n_experts <= 32) ROM_ROUTE_LAUNCH(32, 1, 1);
+  else ROM_ROUTE_LAUNCH(64, 1, 1);
 #undef ROM_ROUTE_LAUNCH
   return hipGetLastError();
 }
