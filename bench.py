@@ -111,6 +111,8 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
     ap.add_argument("--no-step", action="store_true",
                     help="skip the extra rom_step measurement (256 sequences x 512 steps, cfg4)")
+    ap.add_argument("--only-step", action="store_true",
+                    help="run only the rom_step measurement and print its JSON object (for profiling)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (a kernel of known traffic, for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -119,6 +121,10 @@ def main():
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.only_step:
+        print(json.dumps({"decode_step": decode_step_rate()}))
+        return
 
     import torch
     from paper_2506_18145_amd import RomLayer, rom_profile_collect, rom_profile_enable
