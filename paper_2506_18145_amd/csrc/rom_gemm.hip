@@ -283,6 +283,18 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
       if constexpr (S == 0) ra0[i] = v; else ra1[i] = v;
     }
   };
+  // 64-row tiles serve launches with a few rows per expert (the recurrent step): every weight is
+  // used once or twice, so it is streamed past the caches (non-temporal) and the activations,
+  // states and routing arrays keep their place in L2 / the infinity cache (measured: -10 % per step)
+  constexpr bool kStreamW = BM == 64;
+  auto load_w = [&](const bf16_t *src) __attribute__((always_inline)) {
+    if constexpr (kStreamW) {
+      const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(src));
+      return make_uint4(t.x, t.y, t.z, t.w);
+    } else {
+      return *reinterpret_cast<const uint4 *>(src);
+    }
+  };
   auto load_b = [&](int k0, auto set) __attribute__((always_inline)) {
     constexpr int S = decltype(set)::value;
     const int k = k0 + k_chunk;
@@ -290,8 +302,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) {
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (!KTAIL || k0 + kBK <= k_len) v = *reinterpret_cast<const uint4 *>(Wp + b_src[i] + k);
-      else if (k_ok) v = *reinterpret_cast<const uint4 *>(Wp + b_src[i] + k);
+      if (!KTAIL || k0 + kBK <= k_len) v = load_w(Wp + b_src[i] + k);
+      else if (k_ok) v = load_w(Wp + b_src[i] + k);
       if constexpr (S == 0) rb0[i] = v; else rb1[i] = v;
     }
   };
