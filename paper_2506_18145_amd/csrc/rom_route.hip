@@ -178,26 +178,38 @@ __global__ __launch_bounds__(kSortBlock) void hist_kernel(const int32_t *__restr
   }
 }
 
-// One block: thread e turns block_counts[:, e] into an exclusive prefix over blocks,
-// then thread 0 builds counts / offsets.
-__global__ __launch_bounds__(64) void offsets_kernel(int32_t *__restrict__ block_counts,
-                                                     int64_t n_blocks, int n_experts,
-                                                     int32_t *__restrict__ counts,
-                                                     int32_t *__restrict__ offsets) {
+// One block of up to 16 waves: wave w turns block_counts[:, e] for e = w, w + 16, ... into an
+// exclusive prefix over blocks, 64 blocks at a time with a wave-wide scan; thread 0 then builds
+// counts / offsets.
+constexpr int kOffsetWaves = 16;
+__global__ __launch_bounds__(kOffsetWaves *kWave) void offsets_kernel(int32_t *__restrict__ block_counts,
+                                                                      int64_t n_blocks, int n_experts,
+                                                                      int32_t *__restrict__ counts,
+                                                                      int32_t *__restrict__ offsets) {
   __shared__ int total[64];
-  const int e = threadIdx.x;
-  if (e < n_experts) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int n_waves = blockDim.x / kWave;
+  for (int e = wave; e < n_experts; e += n_waves) {
     int run = 0;
-    for (int64_t b = 0; b < n_blocks; ++b) {
-      const int c = block_counts[b * n_experts + e];
-      block_counts[b * n_experts + e] = run;
-      run += c;
+    for (int64_t b0 = 0; b0 < n_blocks; b0 += kWave) {
+      const int64_t b = b0 + lane;
+      const int c = b < n_blocks ? block_counts[b * n_experts + e] : 0;
+      int incl = c;
+#pragma unroll
+      for (int d = 1; d < kWave; d <<= 1) {
+        const int up = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += up;
+      }
+      if (b < n_blocks) block_counts[b * n_experts + e] = run + incl - c;
+      run += __shfl(incl, kWave - 1, kWave);
     }
-    total[e] = run;
-    counts[e] = run;
+    if (lane == 0) {
+      total[e] = run;
+      counts[e] = run;
+    }
   }
   __syncthreads();
-  if (e == 0) {
+  if (threadIdx.x == 0) {
     int run = 0;
     for (int i = 0; i < n_experts; ++i) { offsets[i] = run; run += total[i]; }
     offsets[n_experts] = run;
@@ -334,8 +346,9 @@ hipError_t launch_permutation(const int32_t *expert_idx, int64_t n_slots, int n_
   const int64_t blocks = route_blocks(n_slots);
   hipLaunchKernelGGL(hist_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kSortBlock), 0, s,
                      expert_idx, n_slots, n_experts, block_counts);
-  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(64), 0, s, block_counts, blocks, n_experts, counts,
-                     offsets);
+  const int offset_waves = n_experts < kOffsetWaves ? n_experts : kOffsetWaves;
+  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(offset_waves * kWave), 0, s, block_counts, blocks, n_experts,
+                     counts, offsets);
   hipLaunchKernelGGL(scatter_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kSortBlock), 0, s,
                      expert_idx, n_slots, n_experts, top_k, block_counts, offsets, perm, inv_perm,
                      tok_of_pos);
