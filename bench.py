@@ -187,6 +187,12 @@ def main():
         else:
             ach = work / (avg_ms * 1e-3) / 1e9
             stages[name] = {"ms": avg_ms, "bound": "hbm", "achieved_gbs": ach, "frac": ach / PEAK_HBM_GBS}
+    # the scan is bound by plain ALU issue, not by HBM: also report it against the fp32 vector peak
+    # (7 flops per (token, channel, state): dt*A, exp, dt*u*B, fma (2), C*h, one add of the reduction)
+    if stages["scan_gate"].get("ms", 0) > 0:
+        fl = 7.0 * n_tok * cfg.d_inner * cfg.d_state
+        ach = fl / (stages["scan_gate"]["ms"] * 1e-3) / 1e12
+        stages["scan_gate"].update({"alu_tflops": ach, "alu_frac": ach / PEAK_ALU_FP32_TFLOPS})
     dom = stages["in_proj"]
     roofline = {"kernel": "in_proj grouped GEMM (gemm_bf16_dma_kernel<256, 4, 2, 0>)", "bound": "mfma",
                 "achieved": dom.get("achieved_tflops"), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
