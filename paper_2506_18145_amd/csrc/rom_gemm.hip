@@ -452,6 +452,7 @@ constexpr int kDmaBK = 64, kDmaRC = kDmaBK / 8, kDmaSlots = 5;
 constexpr bool kUseDma = true;
 constexpr int kSkinnyMinWgs = 100;
 constexpr bool kUseSmallK = true;
+constexpr int kBigWM = 4, kBigWN = 2;     // wave layout of the 256x256 DMA tile
 
 __device__ __forceinline__ void dma_load_16(unsigned lds_addr, unsigned voff, const void *base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n"
@@ -462,15 +463,15 @@ __device__ __forceinline__ void dma_load_16(unsigned lds_addr, unsigned voff, co
 // the five 32 KiB ring slots; the weight half slabs just fill less of theirs.  grid.y slices the
 // inner dimension (fp32 partial sums, plain epilogue only).
 template <int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a) {
-  constexpr int BM = 256;
+__global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_dma_kernel(const GemmArgs a) {
+  constexpr int BM = 256, NW = WM * WN;
   static_assert(kDmaSlots == 4 || kDmaSlots == 5, "ring of four or five half-slab slots");
-  static_assert(WM * WN == 8 && BN <= BM && BN % (32 * WN) == 0, "eight waves, 32-wide MFMA tiles");
+  static_assert((NW == 16 || NW == 8 || NW == 4) && BN <= BM && BN % (32 * WN) == 0, "4, 8 or 16 waves, 32-wide MFMA tiles");
   constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
   constexpr int kSlotChunks = BM * kDmaRC;                    // 16-byte chunks per ring slot
   constexpr int kSlotBytes = kSlotChunks * 16;                // 32 KiB
-  constexpr int kAInstr = BM / 64;                            // DMA instructions per wave and half slab: 8 rows each
-  constexpr int kWInstr = (BN + 63) / 64;                     // (rows past BN are clamped re-reads into unused slot space)
+  constexpr int kAInstr = BM / (8 * NW);                      // DMA instructions per wave and half slab: 8 rows each
+  constexpr int kWInstr = (BN + 8 * NW - 1) / (8 * NW);       // (rows past BN are clamped re-reads into unused slot space)
 
   extern __shared__ __attribute__((aligned(16))) uint4 smem[];
   const TileCoord tc = locate_tile(a, BM, BN);
@@ -799,8 +800,8 @@ hipError_t launch_dma(const GemmArgs &a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_bf16_dma_kernel<BN, WM, WN, EPI>), dim3(grid_tiles(a, 256, BN), a.k_splits), dim3(512),
-                     kSmem, s, a);
+  hipLaunchKernelGGL((gemm_bf16_dma_kernel<BN, WM, WN, EPI>), dim3(grid_tiles(a, 256, BN), a.k_splits),
+                     dim3(WM * WN * 64), kSmem, s, a);
   return hipGetLastError();
 }
 // the DMA kernel addresses both operands with unsigned 32-bit byte offsets and walks whole 64-wide slabs
@@ -815,7 +816,7 @@ hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
   // a short inner dimension makes the launch epilogue-bound: smaller tiles put several
   // workgroups on a CU so that loads, MFMAs and stores of different tiles overlap
   if (rows_per_group >= 1024 && a.N >= 256 && a.K > 256) {
-    if (dma_ok(a) && a.k_splits == 1) return launch_dma<256, 4, 2, EPI>(a, s);
+    if (dma_ok(a) && a.k_splits == 1) return launch_dma<256, kBigWM, kBigWN, EPI>(a, s);
     return launch_mfma<256, 256, 4, 2, EPI>(a, s);
   }
   if (rows_per_group >= 96) return launch_mfma<128, 128, 2, 2, EPI>(a, s);
