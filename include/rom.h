@@ -4,8 +4,10 @@
  * C ABI.  Every pointer in rom_weights and every tensor / workspace argument is a
  * DEVICE pointer to caller-owned memory unless a comment says "host".  The library
  * allocates no device memory, launches everything asynchronously on the caller's HIP
- * stream and never synchronises (the rom_profile_* helpers excepted).  Buffers must
- * stay valid until the stream has passed the end of the call.
+ * stream (with rom_set_segments >= 2 also on one stream of its own, which it forks from and
+ * joins back into the caller's stream inside the call) and never synchronises (the
+ * rom_profile_* helpers excepted).  Buffers must stay valid until the stream has passed the
+ * end of the call.
  *
  * The layer (paper Sec. 4.2, Eq. (9)-(13), on top of the Mamba layer of Sec. 3.1,
  * Eq. (1)-(6)):
