@@ -214,6 +214,7 @@ __global__ __launch_bounds__(256) void conv_silu_kernel(
 // the chunks before it.  The recurrence is linear in h, so this is the same arithmetic regrouped.
 // Beyond one workgroup per CU the state-only pass costs as much as the better issue rate gains.
 constexpr int kScanTile = 64;
+constexpr bool kScanDouble = true;
 constexpr int kScanGroups = kScanTile / 16;
 constexpr int kScanCh = 16;
 constexpr int kBcPitch = kScanTile + 4;     // floats; keeps 16-byte alignment of the row reads
@@ -232,10 +233,10 @@ constexpr int kDppRowBcast0 = 0x150;    // row_newbcast:0 (+j for lane j of the 
 // once when a tile is parked is cheaper than converting in the issue-bound inner loop.
 constexpr int kChPitch = kScanCh + 4;
 
-struct __attribute__((aligned(16))) ScanSmem {
+struct __attribute__((aligned(16))) ScanSmem {     // one tile of inputs
   float dt[kScanTile][kChPitch];
   float u[kScanTile][kChPitch];
-  float zg[kScanTile][kChPitch];        // z on the way in; the lane that read z_t puts g_t in its place
+  float zg[kScanTile][kChPitch];        // z on the way in; with a single tile in LDS the lane that read z_t puts g_t in its place
   float bc[32][kBcPitch];               // [B_0..B_15, C_0..C_15][step]
 };
 
@@ -393,14 +394,18 @@ __device__ __forceinline__ void scan_park(ScanSmem &sm, const ScanStage<T> &r, i
 
 // grid: (d_inner / 16, B, chunks handled by this pass).  chunk_q / chunk_p: f32
 // [B][n_chunks - 1][d_inner][16], end state from zero and total decay of every chunk but the last.
-template <typename T, bool kStateOnly>
+// NB = 1: one tile in LDS (24 KiB, six blocks per CU); NB = 2: two tiles and two g tiles (58 KiB):
+// the next tile is parked while this one is computed and a tile costs one barrier instead of two,
+// which pays when the launch has no more than one block per CU anyway.
+template <typename T, bool kStateOnly, int NB>
 __global__ __launch_bounds__(256) void scan_kernel(
     const T *__restrict__ u, const T *__restrict__ dt, const float *__restrict__ bc,
     const T *__restrict__ z, int64_t ld_z, const float *__restrict__ A_log,
     const float *__restrict__ D, const float *__restrict__ h_in, float *__restrict__ h_out,
     T *__restrict__ g, int64_t L, int d_inner, int64_t chunk_len, int n_chunks,
     float *__restrict__ chunk_q, float *__restrict__ chunk_p) {
-  __shared__ ScanSmem sm;
+  __shared__ ScanSmem tiles[NB];
+  __shared__ float g_tiles[NB == 2 ? 2 : 1][NB == 2 ? kScanTile : 1][kChPitch];
   const int tid = threadIdx.x;
   const int n = tid & 15;            // state index = lane inside the DPP row
   const int cl = tid >> 4;           // channel inside the block
@@ -440,10 +445,12 @@ __global__ __launch_bounds__(256) void scan_kernel(
     scan_fetch<T, kStateOnly, false>(st, dt_b, u_b, z_b, bc_b, t_begin, t_end, d_inner, ld_z, tid);
   else
     scan_fetch<T, kStateOnly, true>(st, dt_b, u_b, z_b, bc_b, t_begin, t_end, d_inner, ld_z, tid);
-  scan_park<T, kStateOnly>(sm, st, tid);
+  scan_park<T, kStateOnly>(tiles[0], st, tid);
   __syncthreads();
 
   for (int64_t ti = 0; ti < n_tiles; ++ti) {
+    ScanSmem &sm = tiles[NB == 2 ? (ti & 1) : 0];
+    float(*g_tile)[kChPitch] = NB == 2 ? g_tiles[ti & 1] : sm.zg;
     const int64_t t0 = t_begin + ti * kScanTile;
     const bool has_next = ti + 1 < n_tiles;
     if (has_next) {     // next tile's inputs travel while this tile is computed
@@ -478,20 +485,21 @@ __global__ __launch_bounds__(256) void scan_kernel(
         }
         const float z_r = sm.zg[s0 + n][cl];
         const float y = transpose_reduce16(hs, cv, n) + d_skip * u_r;
-        sm.zg[s0 + n][cl] = y * silu_f32(z_r);
+        g_tile[s0 + n][cl] = y * silu_f32(z_r);
       }
     }
-    __syncthreads();     // everyone is done reading the tile; g is complete
+    if (NB == 2 && has_next) scan_park<T, kStateOnly>(tiles[(ti + 1) & 1], st, tid);
+    __syncthreads();     // everyone is done reading the tile; g is complete (and the next tile parked)
     if (!kStateOnly) {   // g of this tile: thread -> (step row, 4 channels), the packet it parks z into
       const int r = tid >> 2, q = (tid & 3) * 4;
       const int64_t t = t0 + r;
       if (t < t_end) {
         Pack<T, 4> pk;
-        pk.from_floats(*reinterpret_cast<const float4 *>(&sm.zg[r][q]));
+        pk.from_floats(*reinterpret_cast<const float4 *>(&g_tile[r][q]));
         pk.store(g_b + t * d_inner + q);
       }
     }
-    if (has_next) {
+    if (NB == 1 && has_next) {
       scan_park<T, kStateOnly>(sm, st, tid);
       __syncthreads();
     }
@@ -679,13 +687,18 @@ static hipError_t scan_dispatch(const T *u, const T *dt, const float *bc, const 
   const int nc = static_cast<int>(ceil_div(L, chunk_len));      // no empty chunk after rounding
   const unsigned gx = static_cast<unsigned>(d_inner / kScanCh), gy = static_cast<unsigned>(B);
   if (nc > 1) {
-    hipLaunchKernelGGL((scan_kernel<T, true>), dim3(gx, gy, nc - 1), dim3(256), 0, s, u, dt, bc,
+    hipLaunchKernelGGL((scan_kernel<T, true, 1>), dim3(gx, gy, nc - 1), dim3(256), 0, s, u, dt, bc,
                        static_cast<const T *>(nullptr), ld_z, A_log, D, static_cast<const float *>(nullptr),
                        static_cast<float *>(nullptr), static_cast<T *>(nullptr), L, d_inner, chunk_len, nc,
                        chunk_q, chunk_p);
   }
-  hipLaunchKernelGGL((scan_kernel<T, false>), dim3(gx, gy, nc), dim3(256), 0, s, u, dt, bc, z, ld_z, A_log,
-                     D, h_in, h_out, g, L, d_inner, chunk_len, nc, chunk_q, chunk_p);
+  // one block per CU or fewer: two tiles in LDS (one barrier per tile); else six small blocks per CU
+  if (kScanDouble && static_cast<int64_t>(gx) * gy * nc <= 256)
+    hipLaunchKernelGGL((scan_kernel<T, false, 2>), dim3(gx, gy, nc), dim3(256), 0, s, u, dt, bc, z, ld_z, A_log,
+                       D, h_in, h_out, g, L, d_inner, chunk_len, nc, chunk_q, chunk_p);
+  else
+    hipLaunchKernelGGL((scan_kernel<T, false, 1>), dim3(gx, gy, nc), dim3(256), 0, s, u, dt, bc, z, ld_z, A_log,
+                       D, h_in, h_out, g, L, d_inner, chunk_len, nc, chunk_q, chunk_p);
   return hipGetLastError();
 }
 
