@@ -302,6 +302,12 @@ __device__ __forceinline__ float bf16_word_get(unsigned int w, int odd) {
 }
 template <> struct Pack<bf16_t, 8> {
   uint4 raw;
+  __device__ __forceinline__ void to_floats(float *f) const {
+    f[0] = bf16_word_get(raw.x, 0); f[1] = bf16_word_get(raw.x, 1);
+    f[2] = bf16_word_get(raw.y, 0); f[3] = bf16_word_get(raw.y, 1);
+    f[4] = bf16_word_get(raw.z, 0); f[5] = bf16_word_get(raw.z, 1);
+    f[6] = bf16_word_get(raw.w, 0); f[7] = bf16_word_get(raw.w, 1);
+  }
   __device__ __forceinline__ void load(const bf16_t *p) { raw = ld_u4(p); }
   __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
   __device__ __forceinline__ void park(float *p) const {      // as floats, 16-byte aligned
@@ -327,6 +333,10 @@ template <> struct Pack<bf16_t, 4> {
 };
 template <> struct Pack<float, 8> {
   float4 lo, hi;
+  __device__ __forceinline__ void to_floats(float *f) const {
+    f[0] = lo.x; f[1] = lo.y; f[2] = lo.z; f[3] = lo.w;
+    f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
+  }
   __device__ __forceinline__ void load(const float *p) {
     lo = ld_f4(p);
     hi = ld_f4(p + 4);
@@ -551,6 +561,49 @@ __global__ __launch_bounds__(256) void scan_step_kernel(
   if (q == 0) g[bc_idx] = from_f32<T>((part + D[ch] * u_r) * silu_f32(to_f32(z[b * ld_z + ch])));
 }
 
+// ------------------------------------------------------------------ sum over the K slots, wide form
+// slot_sum_kernel with eight columns per thread and 16-byte accesses (n_cols, ld_src, ld_dst multiples of 8,
+// 16-byte aligned bases): the scalar form above moves two or four bytes per lane and reaches half
+// the bandwidth
+template <typename TS, typename TD>
+__global__ __launch_bounds__(256) void slot_sum8_kernel(const TS *__restrict__ src, int64_t ld_src,
+                                                        TD *__restrict__ dst, int64_t ld_dst,
+                                                        const int32_t *__restrict__ inv_perm,
+                                                        int64_t n_tokens, int top_k, int n_cols,
+                                                        const float *__restrict__ bias, int softplus) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int groups = n_cols / 8;
+  if (idx >= n_tokens * groups) return;
+  const int64_t n = idx / groups;
+  const int c = static_cast<int>(idx % groups) * 8;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+  for (int k = 0; k < top_k; ++k) {
+    const int64_t row = inv_perm[n * top_k + k];
+    Pack<TS, 8> v;
+    v.load(src + row * ld_src + c);
+    float f[8];
+    v.to_floats(f);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] += f[i];
+  }
+  if (bias) {
+    const float4 b0 = ld_f4(bias + c), b1 = ld_f4(bias + c + 4);
+    acc[0] += b0.x; acc[1] += b0.y; acc[2] += b0.z; acc[3] += b0.w;
+    acc[4] += b1.x; acc[5] += b1.y; acc[6] += b1.z; acc[7] += b1.w;
+  }
+  if (softplus) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = softplus_f32(acc[i]);
+  }
+  Pack<TD, 4> lo, hi;
+  lo.from_floats(make_float4(acc[0], acc[1], acc[2], acc[3]));
+  hi.from_floats(make_float4(acc[4], acc[5], acc[6], acc[7]));
+  lo.store(dst + n * ld_dst + c);
+  hi.store(dst + n * ld_dst + c + 4);
+}
+
 // ------------------------------------------------------------------ combine, Eq. (12)
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(const T *__restrict__ op,
@@ -588,11 +641,21 @@ inline dim3 grid1d(int64_t work, int block) { return dim3(static_cast<unsigned>(
 hipError_t launch_slot_sum(int src_is_f32, int dst_is_f32, const void *src, int64_t ld_src, void *dst,
                            int64_t ld_dst, const int32_t *inv_perm, int64_t n_tokens, int top_k,
                            int n_cols, const float *bias, int softplus, hipStream_t s) {
-  const dim3 grid = grid1d(n_tokens * (n_cols / 2), 256);
+  const bool wide = n_cols % 8 == 0 && ld_src % 8 == 0 && ld_dst % 8 == 0 &&
+                    reinterpret_cast<uintptr_t>(src) % 16 == 0 && reinterpret_cast<uintptr_t>(dst) % 16 == 0 &&
+                    (!bias || reinterpret_cast<uintptr_t>(bias) % 16 == 0);
+  const dim3 grid = wide ? grid1d(n_tokens * (n_cols / 8), 256) : grid1d(n_tokens * (n_cols / 2), 256);
 #define ROM_SS(TS, TD)                                                                            \
-  hipLaunchKernelGGL((slot_sum_kernel<TS, TD>), grid, dim3(256), 0, s, static_cast<const TS *>(src), \
-                     ld_src, static_cast<TD *>(dst), ld_dst, inv_perm, n_tokens, top_k, n_cols,    \
-                     bias, softplus)
+  do {                                                                                            \
+    if (wide)                                                                                     \
+      hipLaunchKernelGGL((slot_sum8_kernel<TS, TD>), grid, dim3(256), 0, s, static_cast<const TS *>(src), \
+                         ld_src, static_cast<TD *>(dst), ld_dst, inv_perm, n_tokens, top_k, n_cols, \
+                         bias, softplus);                                                         \
+    else                                                                                          \
+      hipLaunchKernelGGL((slot_sum_kernel<TS, TD>), grid, dim3(256), 0, s, static_cast<const TS *>(src), \
+                         ld_src, static_cast<TD *>(dst), ld_dst, inv_perm, n_tokens, top_k, n_cols, \
+                         bias, softplus);                                                         \
+  } while (0)
   if (src_is_f32 && dst_is_f32) ROM_SS(float, float);
   else if (src_is_f32) ROM_SS(float, bf16_t);
   else if (dst_is_f32) ROM_SS(bf16_t, float);
