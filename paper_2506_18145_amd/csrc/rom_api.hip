@@ -135,7 +135,7 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   p.dt_low = take(N * R * b);
   p.bc = take(N * 32 * 4);
   p.dt = take(N * De * b);
-  p.dt_raw = (multi && routed_xdt) ? take(S * De * 4) : kNone;
+  p.dt_raw = (multi && routed_xdt) ? take(S * De * b) : kNone;   // per-slot dt pre-activations, in T like every expert output
   p.g = take(N * De * b);
   p.op_sorted = multi ? take(S * Dm * b) : kNone;
   p.conv_tmp = take(static_cast<size_t>(n_seq) * De * 3 * 4);
@@ -435,9 +435,9 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
     if (routed_xdt && multi) {
       ga.A = at(p.dt_low); ga.a_rows = tok_of_pos;
       routed(ga);
-      ga.C = at(p.dt_raw); ga.c_is_f32 = 1;
+      ga.C = at(p.dt_raw);     // one expert's output per slot, stored in T as in_proj's; summed in fp32 below
       ROM_TRY(launch_grouped_gemm(ga, st));
-      ROM_TRY(launch_slot_sum(1, eb == 4, at(p.dt_raw), De, at(p.dt) + tok0 * De * eb, De, inv_perm + tok0 * K,
+      ROM_TRY(launch_slot_sum(eb == 4, eb == 4, at(p.dt_raw), De, at(p.dt) + tok0 * De * eb, De, inv_perm + tok0 * K,
                               n_tok, K, De, w->dt_bias, 1, st));
     } else {
       if (routed_xdt) {

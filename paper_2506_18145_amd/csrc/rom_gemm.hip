@@ -599,7 +599,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_dma_kernel(const GemmAr
 // workgroups (16 waves) share a CU.
 constexpr int kSkBM = 512, kSkBN = 128, kSkWaves = 8;
 
-template <int KSTEPS>
+// PLAIN: no bias, no softplus (the per-slot outputs of K > 1, which the slot sum adds up and activates).
+template <int KSTEPS, bool PLAIN>
 __global__ __launch_bounds__(kSkWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 8)))
 void gemm_bf16_smallk_kernel(const GemmArgs a) {
   constexpr int KC = KSTEPS * 2;                       // 16-byte chunks per row of A / W
@@ -625,7 +626,7 @@ void gemm_bf16_smallk_kernel(const GemmArgs a) {
     const u32x4_t v = *reinterpret_cast<const u32x4_t *>(Wp + static_cast<int64_t>(n) * a.K + c * 8);
     Ws[r * KC + (c ^ ((r >> kSwzShift) & (KC - 1)))] = make_uint4(v.x, v.y, v.z, v.w);
   }
-  if (tid < kSkBN) bias_s[tid] = a.bias[(tc.n0 + tid < a.N) ? tc.n0 + tid : a.N - 1];
+  if (tid < kSkBN) bias_s[tid] = PLAIN ? 0.0f : a.bias[(tc.n0 + tid < a.N) ? tc.n0 + tid : a.N - 1];
   __syncthreads();
 
   const int frag_row = lane & 31, frag_half = lane >> 5;
@@ -670,8 +671,13 @@ void gemm_bf16_smallk_kernel(const GemmArgs a) {
           const int lcol = j * 32 + q * 8 + frag_half * 4;
           const float4 b4 = *reinterpret_cast<const float4 *>(bias_s + h * kHalf + lcol);
           uint2 pk;
-          pk.x = pack_bf16x2(softplus_fast(acc[j][4 * q] + b4.x), softplus_fast(acc[j][4 * q + 1] + b4.y));
-          pk.y = pack_bf16x2(softplus_fast(acc[j][4 * q + 2] + b4.z), softplus_fast(acc[j][4 * q + 3] + b4.w));
+          if constexpr (PLAIN) {
+            pk.x = pack_bf16x2(acc[j][4 * q], acc[j][4 * q + 1]);
+            pk.y = pack_bf16x2(acc[j][4 * q + 2], acc[j][4 * q + 3]);
+          } else {
+            pk.x = pack_bf16x2(softplus_fast(acc[j][4 * q] + b4.x), softplus_fast(acc[j][4 * q + 1] + b4.y));
+            pk.y = pack_bf16x2(softplus_fast(acc[j][4 * q + 2] + b4.z), softplus_fast(acc[j][4 * q + 3] + b4.w));
+          }
           *reinterpret_cast<uint2 *>(stage + frag_row * kPitch + lcol * 2) = pk;
         }
       }
@@ -776,17 +782,17 @@ hipError_t launch_mfma(const GemmArgs &a, hipStream_t s) {
   return launch_mfma_k<BM, BN, WM, WN, EPI, true>(a, s);
 }
 
-template <int KSTEPS>
+template <int KSTEPS, bool PLAIN>
 hipError_t launch_smallk(const GemmArgs &a, hipStream_t s) {
   constexpr int kSmem = kSkBN * KSTEPS * 2 * 16 + kSkBN * 4 + kSkWaves * 32 * (kSkBN + 16);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_smallk_kernel<KSTEPS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_smallk_kernel<KSTEPS, PLAIN>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_bf16_smallk_kernel<KSTEPS>), dim3(grid_tiles(a, kSkBM, kSkBN)), dim3(kSkWaves * 64), kSmem, s, a);
+  hipLaunchKernelGGL((gemm_bf16_smallk_kernel<KSTEPS, PLAIN>), dim3(grid_tiles(a, kSkBM, kSkBN)), dim3(kSkWaves * 64), kSmem, s, a);
   return hipGetLastError();
 }
 
@@ -873,13 +879,19 @@ hipError_t launch_grouped_gemm(const GemmArgs &args, hipStream_t s) {
   }
   if (a.bias) {
     if (kUseSmallK && a.lda >= a.K && a.M < (1ll << 31)) {
-      if (a.K == 128) return launch_smallk<8>(a, s);
-      if (a.K == 64) return launch_smallk<4>(a, s);
-      if (a.K == 32) return launch_smallk<2>(a, s);
+      if (a.K == 128) return launch_smallk<8, false>(a, s);
+      if (a.K == 64) return launch_smallk<4, false>(a, s);
+      if (a.K == 32) return launch_smallk<2, false>(a, s);
     }
     return launch_mfma_tiles<kEpiBiasSoftplus>(a, s);
   }
   if (a.row_scale) return launch_mfma_tiles<kEpiRowScale>(a, s);
+  // short inner dimension, many rows, wide output: the streaming kernel without its activation
+  if (kUseSmallK && a.lda >= a.K && a.M < (1ll << 31) && a.M >= 4096 && a.N >= 1024) {
+    if (a.K == 128) return launch_smallk<8, true>(a, s);
+    if (a.K == 64) return launch_smallk<4, true>(a, s);
+    if (a.K == 32) return launch_smallk<2, true>(a, s);
+  }
   return launch_mfma_tiles<kEpiPlain>(a, s);
 }
 
