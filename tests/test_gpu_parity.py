@@ -58,6 +58,9 @@ def test_small_layers(kw):
     dict(batch=1, seq_len=4999, d_model=512, d_inner=1024, dt_rank=32, cfg_id=62,
          router_bias=(0.5, 0.0, 0.0, -50.0)),
     dict(batch=1, seq_len=4500, d_model=320, d_inner=640, dt_rank=64, routed_xdt=False, cfg_id=63),
+    # big tiles with a ragged last column tile (N = 2112), and an inner dimension that is not a
+    # multiple of the 64-wide slab (d_inner = 1056: K-tail path of the register-staged 256x256 kernel)
+    dict(batch=1, seq_len=4200, d_model=512, d_inner=1056, dt_rank=48, cfg_id=64),
 ])
 def test_medium_layers_big_tile_kernels(kw):
     cfg = small_cfg(**kw)
