@@ -109,6 +109,34 @@ def test_segmented_pipeline_is_deterministic_and_matches_unsegmented_routing():
     assert rel_err(seg1["out"], base["out"]) <= TOL["bf16"] * 0.25
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_shapes(seed):
+    """Seeded random layer shapes (sizes off every tile grid, many and few experts, both dtypes,
+    with and without incoming state, cut into segments or not) against the oracle."""
+    import random
+    from paper_2506_18145_amd import rom_set_segments
+    rng = random.Random(seed)
+    for i in range(10):
+        E = rng.choice([1, 2, 3, 5, 8, 12, 16, 33, 64])
+        kw = dict(name=f"random-{seed}-{i}", cfg_id=700 + 20 * seed + i, batch=rng.choice([1, 1, 2, 3, 5]),
+                  seq_len=rng.choice([1, 2, 7, 31, 64, 65, 130, 257, 700, 1500]),
+                  d_model=8 * rng.randint(4, 80), d_inner=16 * rng.randint(2, 70), d_state=16, d_conv=4,
+                  dt_rank=rng.choice([1, 3, 8, 16, 24, 32, 48, 64, 128]), n_experts=E,
+                  top_k=rng.randint(1, min(E, 4)), dtype=rng.choice(["bf16", "bf16", "fp32"]),
+                  gate_mode=rng.choice([0, 1]), routed_xdt=rng.choice([True, True, False]))
+        cfg = RomConfig(**kw)
+        seg = rng.choice([0, 0, 2, 3])
+        cs, ss = make_states(cfg) if rng.choice([False, True]) else (None, None)
+        print(f"[{cfg.name}] B={cfg.batch} L={cfg.seq_len} Dm={cfg.d_model} De={cfg.d_inner} R={cfg.dt_rank} "
+              f"E={E} K={cfg.top_k} {cfg.dtype} segments={seg}", flush=True)
+        rom_set_segments(seg)
+        try:
+            _, gpu, x, w = run_layer(cfg, cs, ss)
+        finally:
+            rom_set_segments(0)
+        compare_layer(cfg, gpu, x, w, cs, ss)
+
+
 def test_carried_state_and_split_sequence():
     cfg = small_cfg(seq_len=150, top_k=2, gate_mode=1)
     cs, ss = make_states(cfg)
