@@ -26,6 +26,7 @@ Readings of the paper taken here (each is also listed in the design notes):
   * Routed x/dt projections (the "Conv, Gate, dt, x, Out" variant of Table 1)
     are indicator sums like Eq. (11); dt_bias is one shared vector.
   * Top-K picks on logits, descending, lowest expert index on ties.
+  * Eq. (16): per-layer term, F normalised by N*K, expectation over the call's tokens.
 """
 from __future__ import annotations
 
@@ -118,6 +119,34 @@ def expert_permutation(idx, n_experts):
         inv_perm[s] = pos
         perm[pos] = s
     return counts, offsets, perm, inv_perm
+
+
+def balance_stats(logits, idx, n_experts, alpha=1.0):
+    """One layer's term of the auxiliary load-balance loss, Eq. (16) (appendix on load balance).
+
+    F[i]     = (slots routed to expert i) / (N * K): the fraction of the dispatched (token, k)
+               slots that expert i receives, so that sum_i F[i] = 1 for every K
+    P_bar[i] = mean over the N tokens of softmax(logits[n, :])[i]  (the full softmax over all
+               E experts, the expectation of Eq. (16) taken over the tokens of the call)
+    loss     = alpha * E * sum_i F[i] * P_bar[i]
+
+    The model-level loss is the sum of this term over the layers.  Readings: the equation's
+    inner index runs over the experts (its printed upper limit N is the number of experts, as the
+    text below it says); F is normalised by N*K rather than N; no routing jitter is applied.
+    Returns (F [E], P_bar [E], loss) in float64.
+    """
+    logits = np.asarray(logits, F64)
+    idx = np.asarray(idx)
+    n, k = idx.shape
+    frac = np.zeros(n_experts, F64)
+    p_bar = np.zeros(n_experts, F64)
+    for i in range(n_experts):
+        frac[i] = np.count_nonzero(idx == i) / float(n * k)
+    p = softmax(logits)
+    for i in range(n_experts):
+        p_bar[i] = p[:, i].sum() / float(n)
+    loss = alpha * n_experts * float(np.dot(frac, p_bar))
+    return frac, p_bar, loss
 
 
 # --------------------------------------------------------------------------

@@ -129,6 +129,64 @@ def test_permutation_invariants():
     assert np.array_equal(perm, np.argsort(idx.ravel(), kind="stable"))
 
 
+def test_balance_stats_hand_worked_example():
+    b = _read_golden_blocks(os.path.join(GOLDEN, "balance_worked_example.txt"))
+    logits = np.log(np.array(b["exp_logits"]))
+    idx = O.topk_select(logits, 2)
+    assert idx.tolist() == np.array(b["expert_idx"], int).tolist()
+    frac, p_bar, loss = O.balance_stats(logits, idx, 3, alpha=1.0)
+    np.testing.assert_allclose(frac, b["F"][0], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(p_bar, b["P_bar"][0], rtol=0, atol=1e-15)
+    assert abs(loss - b["loss"][0][0]) < 1e-15
+
+
+def test_balance_stats_closed_forms_and_brute_force():
+    """Eq. (16): flat router -> alpha whatever the counts; a router that spreads tokens evenly
+    with near-certain choices -> alpha; a collapsed router -> alpha * E; and a token-by-token
+    accumulation with math.exp on random logits."""
+    import math
+    E, N, alpha = 5, 40, 1e-3
+    flat = np.zeros((N, E))
+    frac, p_bar, loss = O.balance_stats(flat, O.topk_select(flat, 1), E, alpha)
+    assert frac.tolist() == [1.0, 0, 0, 0, 0]            # ties go to expert 0
+    np.testing.assert_allclose(p_bar, 1.0 / E, atol=1e-15)
+    assert abs(loss - alpha) < 1e-18
+    even = np.full((N, E), -60.0)
+    even[np.arange(N), np.arange(N) % E] = 60.0
+    frac, p_bar, loss = O.balance_stats(even, O.topk_select(even, 1), E, alpha)
+    np.testing.assert_allclose(frac, 1.0 / E, atol=1e-15)
+    np.testing.assert_allclose(p_bar, 1.0 / E, atol=1e-15)
+    assert abs(loss - alpha) < 1e-15
+    collapsed = np.full((N, E), -60.0)
+    collapsed[:, 3] = 60.0
+    frac, p_bar, loss = O.balance_stats(collapsed, O.topk_select(collapsed, 1), E, alpha)
+    assert abs(loss - alpha * E) < 1e-15 and frac[3] == 1.0
+
+    rng = np.random.default_rng(99)
+    for K in (1, 2, 5):
+        logits = rng.standard_normal((N, E)) * 2.0
+        idx = O.topk_select(logits, K)
+        frac, p_bar, loss = O.balance_stats(logits, idx, E, alpha)
+        cnt, acc = [0] * E, [0.0] * E
+        for n in range(N):
+            ex = [math.exp(v) for v in logits[n]]
+            tot = sum(ex)
+            for e in range(E):
+                acc[e] += ex[e] / tot
+            for e in sorted(range(E), key=lambda e: (-logits[n, e], e))[:K]:
+                cnt[e] += 1
+        assert abs(sum(frac) - 1.0) < 1e-12 and abs(sum(p_bar) - 1.0) < 1e-12
+        np.testing.assert_allclose(frac, [c / (N * K) for c in cnt], atol=1e-15)
+        np.testing.assert_allclose(p_bar, [a / N for a in acc], atol=1e-14)
+        assert abs(loss - alpha * E * sum(c / (N * K) * a / N for c, a in zip(cnt, acc))) < 1e-15
+        # K = E: every expert gets every token, F is uniform and the loss is alpha again
+        if K == E:
+            assert abs(loss - alpha) < 1e-15
+    # the counts agree with the grouping the layer uses
+    counts, _, _, _ = O.expert_permutation(idx, E)
+    np.testing.assert_allclose(frac, counts / float(N * 5), atol=1e-15)
+
+
 def test_routing_is_per_token():
     """Permuting the tokens permutes the decisions (the router sees one token at a time)."""
     cfg = tiny_cfg(batch=1, seq_len=20, n_experts=4, top_k=2)
