@@ -101,55 +101,31 @@ def decode_step_rate(n_steps=512):
             "frac": (w_bytes + s_bytes) / (dt / n_steps) / 1e9 / PEAK_HBM_GBS}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
-    ap.add_argument("--no-step", action="store_true",
-                    help="skip the extra rom_step measurement (256 sequences x 512 steps, cfg4)")
-    ap.add_argument("--only-step", action="store_true",
-                    help="run only the rom_step measurement and print its JSON object (for profiling)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run three plain 1 GiB device copies (a kernel of known traffic, for "
-                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
-              "use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
-    if args.only_step:
-        print(json.dumps({"decode_step": decode_step_rate()}))
-        return
-
+def time_forward(cfg, steps, warmup, calibrate_copy=False):
+    """K timed calls of rom_layer_forward on resident inputs.  Returns (ms per call, ms per call
+    without the stage events, per-stage dict)."""
     import torch
-    from paper_2506_18145_amd import RomLayer, rom_profile_collect, rom_profile_enable
-    from rom_synth import get_config, make_input, make_weights
+    from paper_2506_18145_amd import RomLayer, rom_layer_forward, rom_profile_collect, rom_profile_enable
+    from rom_synth import make_input, make_weights
 
-    cfg = get_config(args.workload)
     layer = RomLayer(cfg, make_weights(cfg), device="cuda:0")
     x = layer.to_device(make_input(cfg))
     B, L = cfg.batch, cfg.seq_len
     out = torch.empty_like(x)
-    from paper_2506_18145_amd import rom_layer_forward
     ws = layer.workspace(B, L)
 
     def step():
         rom_layer_forward(layer.dims, layer.weights, x, B, L, None, None, out, None, None, ws)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
 
     # timed region: K calls, stage events recorded by the library on the same stream
-    rom_profile_enable(args.steps)
+    rom_profile_enable(steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -159,23 +135,35 @@ def main():
     # the same K calls without the event records, for the record-keeping overhead
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     elapsed_plain = time.perf_counter() - t1
 
-    if args.calibrate_copy:
+    # load-balance statistics (Eq. (16)) from the logits and counts the last call left behind
+    lg, ct = layer.ws_view("logits", B, L), layer.ws_view("counts", B, L)
+    from paper_2506_18145_amd import rom_balance_stats
+    stats = layer.balance_stats(lg, ct, 1e-3)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(50):
+        rom_balance_stats(layer.dims, lg, ct, B * L, 1e-3, stats[0], stats[1], stats[2], ws)
+    e1.record()
+    torch.cuda.synchronize()
+    counts = ct.cpu().tolist()
+    balance = {"us_per_call": e0.elapsed_time(e1) * 1e3 / 50, "loss_term_alpha_1e-3": float(stats[2].cpu()[0]),
+               "max_over_mean_count": max(counts) / (sum(counts) / len(counts))}
+
+    if calibrate_copy:
         src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")     # 1 GiB
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    ms_per_step = elapsed * 1e3 / args.steps
     n_tok = B * L
-    model = stage_model(cfg)
     stages = {}
-    for name, (bound, work) in model.items():
+    for name, (bound, work) in stage_model(cfg).items():
         avg_ms = stage_ms[name] / max(n_calls, 1)
         if avg_ms <= 0 or work == 0:
             stages[name] = {"ms": avg_ms}
@@ -193,6 +181,43 @@ def main():
         fl = 7.0 * n_tok * cfg.d_inner * cfg.d_state
         ach = fl / (stages["scan_gate"]["ms"] * 1e-3) / 1e12
         stages["scan_gate"].update({"alu_tflops": ach, "alu_frac": ach / PEAK_ALU_FP32_TFLOPS})
+    return elapsed * 1e3 / steps, elapsed_plain * 1e3 / steps, stages, balance
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
+    ap.add_argument("--no-step", action="store_true",
+                    help="skip the extra rom_step measurement (256 sequences x 512 steps, cfg4)")
+    ap.add_argument("--no-shared-xdt", action="store_true",
+                    help="skip the extra measurement of the shared x/dt variant of the workload")
+    ap.add_argument("--only-step", action="store_true",
+                    help="run only the rom_step measurement and print its JSON object (for profiling)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (a kernel of known traffic, for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    if args.only_step:
+        print(json.dumps({"decode_step": decode_step_rate()}))
+        return
+
+    from dataclasses import replace
+    from rom_synth import get_config
+
+    cfg = get_config(args.workload)
+    B, L = cfg.batch, cfg.seq_len
+    n_tok = B * L
+    ms_per_step, ms_plain, stages, balance = time_forward(cfg, args.steps, args.warmup, args.calibrate_copy)
     dom = stages["in_proj"]
     roofline = {"kernel": "in_proj grouped GEMM (gemm_bf16_dma_kernel<256, 4, 2, 0>)", "bound": "mfma",
                 "achieved": dom.get("achieved_tflops"), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
@@ -205,7 +230,7 @@ def main():
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
-        "ms_per_step_without_stage_events": elapsed_plain * 1e3 / args.steps,
+        "ms_per_step_without_stage_events": ms_plain,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: RoM layer forward, B={B}, L={L}, d_model={cfg.d_model}, "
@@ -215,6 +240,16 @@ def main():
         "roofline": roofline,
         "stages": stages,
     }
+    result["balance_stats"] = balance
+    if not args.no_shared_xdt:
+        # the paper's default variant (Sec. 4.3, design choices): x and dt projections shared by all experts, so
+        # those two stages are plain GEMMs; same shapes and inputs otherwise
+        shared = replace(cfg, name=cfg.name + "-shared-xdt", routed_xdt=False)
+        ms_s, _, stages_s, _ = time_forward(shared, max(args.steps // 2, 1), args.warmup)
+        result["shared_xdt_variant"] = {
+            "workload": f"{cfg.name} with one shared x/dt projection (E_x = 1)", "ms_per_step": ms_s,
+            "tokens_per_s": n_tok / (ms_s * 1e-3),
+            "stages_ms": {k: v["ms"] for k, v in stages_s.items()}}
     if not args.no_step:
         result["decode_step"] = decode_step_rate()
     if not args.no_cpu_baseline:

@@ -131,6 +131,25 @@ ROM_API int rom_route(const rom_dims *dims, const rom_weights *w, const void *x,
               int32_t *perm, int32_t *inv_perm, float *logits,
               void *ws, size_t ws_bytes, void *hip_stream);
 
+/* Load-balance statistics of one layer's routing decision, Eq. (16) (appendix on the auxiliary
+ * load-balance loss; the layer itself never uses them):
+ *   frac[i]      = counts[i] / (N * K)              share of the (token, k) slots sent to expert i
+ *   mean_prob[i] = (1/N) sum_n softmax(logits[n, :])[i]   full softmax over all E experts
+ *   loss[0]      = alpha * E * sum_i frac[i] * mean_prob[i]
+ * The model-level loss of Eq. (16) is the sum of loss[0] over the layers.
+ *   logits     f32 [N, E]  as written by rom_route, or by rom_layer_forward / rom_step into the
+ *                          workspace region rom_ws_layout.logits (N = B * L)
+ *   counts     i32 [E]     as written by rom_route, or the workspace region rom_ws_layout.counts
+ *   frac, mean_prob  f32 [E]  out;  loss  f32 [1]  out   (all device pointers)
+ *   ws/ws_bytes  workspace of at least rom_workspace_bytes(dims, N, 1).  It may be the workspace
+ *                the logits and counts live in: the scratch this call uses lies at the same offset
+ *                for every (B, L) with B * L = N and overlaps no region named in rom_ws_layout.
+ * The sums are taken in a fixed order: repeated calls give identical bits.
+ * N <= 0 is ROM_E_INVAL (the mean over no tokens is undefined). */
+ROM_API int rom_balance_stats(const rom_dims *dims, const float *logits, const int32_t *counts,
+                      int64_t N, float alpha, float *frac, float *mean_prob, float *loss,
+                      void *ws, size_t ws_bytes, void *hip_stream);
+
 /* The whole layer, Eq. (9)-(13).
  *   x              T   [B, L, d_model]
  *   conv_state_in  f32 [B, d_inner, d_conv-1] oldest first, or NULL (zeros): the conv-branch

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     RomError,
     RomLayer,
     load_library,
+    rom_balance_stats,
     rom_layer_forward,
     rom_profile_collect,
     rom_profile_enable,

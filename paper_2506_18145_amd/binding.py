@@ -54,6 +54,8 @@ def load_library() -> ctypes.CDLL:
     lib.rom_route.restype = ctypes.c_int
     lib.rom_route.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64,
                               P, P, P, P, P, P, P, P, SZ, P]
+    lib.rom_balance_stats.restype = ctypes.c_int
+    lib.rom_balance_stats.argtypes = [ctypes.POINTER(RomDims), P, P, I64, ctypes.c_float, P, P, P, P, SZ, P]
     lib.rom_layer_forward.restype = ctypes.c_int
     lib.rom_layer_forward.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64, I64,
                                       P, P, P, P, P, P, SZ, P]
@@ -115,6 +117,13 @@ def rom_route(dims, weights, x, expert_idx, gate, counts, offsets, perm, inv_per
         _ptr(gate), _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv_perm), _ptr(logits), _ptr(ws),
         ws.numel() * ws.element_size() if ws is not None else 0, _stream())
     _check(code, "rom_route")
+
+
+def rom_balance_stats(dims, logits, counts, n_tokens, alpha, frac, mean_prob, loss, ws):
+    code = load_library().rom_balance_stats(
+        ctypes.byref(dims), _ptr(logits), _ptr(counts), n_tokens, alpha, _ptr(frac), _ptr(mean_prob),
+        _ptr(loss), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check(code, "rom_balance_stats")
 
 
 def rom_layer_forward(dims, weights, x, B, L, conv_state_in, ssm_state_in, out, conv_state_out,
@@ -224,6 +233,16 @@ class RomLayer:
         rom_route(d, self.weights, x, res["expert_idx"], res["gate"], res["counts"], res["offsets"],
                   res["perm"], res["inv_perm"], res["logits"], self.workspace(max(n, 1), 1))
         return res
+
+    def balance_stats(self, logits: torch.Tensor, counts: torch.Tensor, alpha: float = 1e-3):
+        """(frac [E], mean_prob [E], loss [1]) of Eq. (16) for router outputs of this layer."""
+        E = self.dims.n_experts
+        n = logits.numel() // E
+        f32 = dict(dtype=torch.float32, device=self.device)
+        frac, mean_prob, loss = torch.empty(E, **f32), torch.empty(E, **f32), torch.empty(1, **f32)
+        rom_balance_stats(self.dims, logits, counts, n, alpha, frac, mean_prob, loss,
+                          self.workspace(max(n, 1), 1))
+        return frac, mean_prob, loss
 
     def forward(self, x: torch.Tensor, conv_state=None, ssm_state=None, return_states=False):
         B, L, _ = x.shape

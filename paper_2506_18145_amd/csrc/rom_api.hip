@@ -60,6 +60,7 @@ Segments plan_segments(const rom_dims *d, int64_t B, int64_t L) {
 struct Plan {                 // byte offsets inside the workspace
   size_t total;
   size_t expert_idx, gate, counts, offsets, perm, inv_perm, tok_of_pos, block_counts, logits;
+  size_t balance_part;        // scratch of rom_balance_stats: placed so that it depends on N, K, E only
   size_t xz, xz_sorted, u, xdbl, dt_low, bc, dt, dt_raw, g, op_sorted, conv_tmp;
   size_t seg_lo, seg_hi, conv_carry, ssm_carry;
   size_t scan_q[kMaxSegments], scan_p[kMaxSegments];
@@ -128,6 +129,7 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   p.tok_of_pos = take(S * 4);
   p.block_counts = take(static_cast<size_t>(route_blocks(static_cast<int64_t>(S))) * E * 4);
   p.logits = take(N * E * 4);
+  p.balance_part = take(balance_scratch_bytes(d->n_experts));
   p.xz = take(N * 2 * De * b);
   p.xz_sorted = multi ? take(S * 2 * De * b) : kNone;
   p.u = take(N * De * b);
@@ -556,6 +558,23 @@ int rom_route(const rom_dims *dims, const rom_weights *w, const void *x, int64_t
                     reinterpret_cast<int32_t *>(base + p.tok_of_pos),
                     reinterpret_cast<int32_t *>(base + p.block_counts), logits,
                     static_cast<hipStream_t>(hip_stream), nullptr);
+}
+
+int rom_balance_stats(const rom_dims *dims, const float *logits, const int32_t *counts, int64_t N,
+                      float alpha, float *frac, float *mean_prob, float *loss, void *ws, size_t ws_bytes,
+                      void *hip_stream) {
+  int rc = check_dims(dims);
+  if (rc != ROM_OK) return rc;
+  if (N <= 0 || !logits || !counts || !frac || !mean_prob || !loss || !ws) return ROM_E_INVAL;
+  if ((reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return ROM_E_INVAL;
+  if (N * dims->top_k > (1ll << 30)) return ROM_E_UNSUPPORTED;
+  Plan p = make_plan(dims, N, 1);
+  if (ws_bytes < p.total) return ROM_E_WORKSPACE;
+  float *partial = reinterpret_cast<float *>(static_cast<char *>(ws) + p.balance_part);
+  return launch_balance_stats(logits, counts, N, dims->n_experts, dims->top_k, alpha, partial, frac,
+                              mean_prob, loss, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? ROM_OK
+             : ROM_E_HIP;
 }
 
 int rom_layer_forward(const rom_dims *dims, const rom_weights *w, const void *x, int64_t B, int64_t L,

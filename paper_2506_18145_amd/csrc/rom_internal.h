@@ -48,6 +48,12 @@ hipError_t launch_permutation(const int32_t *expert_idx, int64_t n_slots, int n_
                               int32_t *block_counts, int32_t *counts, int32_t *offsets,
                               int32_t *perm, int32_t *inv_perm, int32_t *tok_of_pos, hipStream_t s);
 
+// load-balance statistics (Eq. (16)); partial: f32 scratch of balance_scratch_bytes(E)
+size_t balance_scratch_bytes(int n_experts);
+hipError_t launch_balance_stats(const float *logits, const int32_t *counts, int64_t n_tokens,
+                                int n_experts, int top_k, float alpha, float *partial, float *frac,
+                                float *mean_prob, float *loss, hipStream_t s);
+
 // ---------------------------------------------------------------- grouped GEMM
 // C[c_row(p), :] = epilogue( A[a_row(p), :] . W[e(p)]^T ),  p = sorted position in [0, M)
 // e(p) from offsets (device, i32 [n_groups+1]); offsets == NULL means one group of M rows.

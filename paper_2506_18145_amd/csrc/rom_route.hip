@@ -309,6 +309,67 @@ __global__ __launch_bounds__(kSortBlock) void permutation_small_kernel(
   }
 }
 
+// Load-balance statistics, Eq. (16).  A wavefront holds 64 / EP tokens at a time (EP = the expert
+// count rounded up to a power of two): lane = token_in_wave * EP + expert.  The softmax maximum
+// and denominator are butterflies inside a group of EP lanes, and each lane keeps the running
+// sum of its own expert's probability.  Blocks own fixed token ranges and their sums are added
+// in block order by the second kernel, so the result is the same on every run.
+constexpr int kBalanceBlock = 256;
+constexpr int kBalanceMaxBlocks = 256;
+
+__global__ __launch_bounds__(kBalanceBlock) void balance_partial_kernel(
+    const float *__restrict__ logits, int64_t n_tokens, int n_experts, int ep,
+    float *__restrict__ partial) {
+  __shared__ float wave_part[kBalanceBlock / kWave][64];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int e = lane & (ep - 1);
+  const int tok_per_wave = kWave / ep;
+  const int64_t wave_id = static_cast<int64_t>(blockIdx.x) * (kBalanceBlock / kWave) + wave;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * (kBalanceBlock / kWave) * tok_per_wave;
+  float acc = 0.0f;
+  // every lane of the wave runs the same number of rounds (the shuffles need all of them)
+  for (int64_t t0 = wave_id * tok_per_wave; t0 < n_tokens; t0 += stride) {
+    const int64_t tok = t0 + lane / ep;
+    const bool live = tok < n_tokens && e < n_experts;
+    const float l = live ? logits[tok * n_experts + e] : -INFINITY;
+    float m = l;
+    for (int o = 1; o < ep; o <<= 1) m = fmaxf(m, __shfl_xor(m, o, kWave));
+    // a group past the last token holds only -inf: keep exp's argument finite there
+    const float p = live ? fast_exp2((l - m) * 1.44269504088896341f) : 0.0f;
+    float den = p;
+    for (int o = 1; o < ep; o <<= 1) den += __shfl_xor(den, o, kWave);
+    if (live) acc += p / den;
+  }
+  for (int o = ep; o < kWave; o <<= 1) acc += __shfl_xor(acc, o, kWave);
+  if (lane < ep) wave_part[wave][lane] = acc;
+  __syncthreads();
+  if (threadIdx.x < n_experts) {
+    float t = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kBalanceBlock / kWave; ++w) t += wave_part[w][threadIdx.x];
+    partial[static_cast<int64_t>(blockIdx.x) * n_experts + threadIdx.x] = t;
+  }
+}
+
+__global__ __launch_bounds__(kWave) void balance_finish_kernel(
+    const float *__restrict__ partial, int n_blocks, const int32_t *__restrict__ counts,
+    int64_t n_tokens, int n_experts, int top_k, float alpha, float *__restrict__ frac,
+    float *__restrict__ mean_prob, float *__restrict__ loss) {
+  const int e = threadIdx.x;
+  float prod = 0.0f;
+  if (e < n_experts) {
+    float t = 0.0f;
+    for (int b = 0; b < n_blocks; ++b) t += partial[static_cast<int64_t>(b) * n_experts + e];
+    const float pm = t / static_cast<float>(n_tokens);
+    const float f = static_cast<float>(counts[e]) / (static_cast<float>(n_tokens) * static_cast<float>(top_k));
+    frac[e] = f;
+    mean_prob[e] = pm;
+    prod = f * pm;
+  }
+  const float total = wave_sum(prod);
+  if (e == 0) *loss = alpha * static_cast<float>(n_experts) * total;
+}
+
 template <typename T>
 hipError_t route_dispatch(const void *x, const void *w_router, const float *b_router,
                           int64_t n_tokens, int d_model, int n_experts, int top_k, int gate_mode,
@@ -348,6 +409,25 @@ hipError_t launch_route_topk(int dtype, const void *x, const void *w_router, con
                                   gate_mode, expert_idx, gate, logits, s);
   return route_dispatch<float>(x, w_router, b_router, n_tokens, d_model, n_experts, top_k, gate_mode,
                                expert_idx, gate, logits, s);
+}
+
+size_t balance_scratch_bytes(int n_experts) {
+  return static_cast<size_t>(kBalanceMaxBlocks) * static_cast<size_t>(n_experts) * sizeof(float);
+}
+
+hipError_t launch_balance_stats(const float *logits, const int32_t *counts, int64_t n_tokens,
+                                int n_experts, int top_k, float alpha, float *partial, float *frac,
+                                float *mean_prob, float *loss, hipStream_t s) {
+  int ep = 1;
+  while (ep < n_experts) ep <<= 1;
+  const int64_t tok_per_block = (kBalanceBlock / kWave) * (kWave / ep);
+  int64_t blocks = ceil_div(n_tokens, tok_per_block);
+  if (blocks > kBalanceMaxBlocks) blocks = kBalanceMaxBlocks;
+  hipLaunchKernelGGL(balance_partial_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBalanceBlock), 0,
+                     s, logits, n_tokens, n_experts, ep, partial);
+  hipLaunchKernelGGL(balance_finish_kernel, dim3(1), dim3(kWave), 0, s, partial, static_cast<int>(blocks),
+                     counts, n_tokens, n_experts, top_k, alpha, frac, mean_prob, loss);
+  return hipGetLastError();
 }
 
 hipError_t launch_permutation(const int32_t *expert_idx, int64_t n_slots, int n_experts, int top_k,

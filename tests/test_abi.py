@@ -137,3 +137,32 @@ def test_segment_knob_is_validated_and_keeps_the_workspace_plan_consistent(lib):
         binding.rom_set_segments(0)
     assert binding.rom_workspace_bytes(d, 1, 1000) == base
 
+
+
+def test_balance_stats_arguments_and_scratch_placement(lib):
+    """rom_balance_stats refuses bad arguments before any launch, and the scratch it takes from the
+    workspace sits between the logits and xz at an offset that depends on N, K and E only."""
+    from paper_2506_18145_amd import binding
+    d = _dims(n_experts=8, top_k=2, n_experts_xdt=8)
+    buf = ctypes.create_string_buffer(4096 + 256)
+    addr = (ctypes.addressof(buf) + 255) // 256 * 256
+    call = lambda dims, lg, ct, n, ws, nbytes: lib.rom_balance_stats(
+        ctypes.byref(dims), lg, ct, n, 1e-3, addr, addr, addr, ws, nbytes, None)
+    assert call(d, addr, addr, 0, addr, 4096) == -1            # no tokens
+    assert call(d, None, addr, 16, addr, 4096) == -1
+    assert call(d, addr, None, 16, addr, 4096) == -1
+    assert call(d, addr, addr, 16, None, 4096) == -1
+    assert call(d, addr, addr, 16, addr + 8, 4096) == -1       # misaligned workspace
+    assert call(d, addr, addr, 16, addr, 4096) == -2           # workspace too small
+    assert call(_dims(top_k=9), addr, addr, 16, addr, 4096) == -1
+    N, E = 1200, 8
+    lays = [binding.rom_workspace_layout(d, 1, N), binding.rom_workspace_layout(d, N, 1),
+            binding.rom_workspace_layout(d, 4, N // 4)]
+    try:
+        binding.rom_set_segments(3)
+        lays.append(binding.rom_workspace_layout(d, 1, N))
+    finally:
+        binding.rom_set_segments(0)
+    for lay in lays:
+        assert lay["logits"] == lays[0]["logits"] and lay["xz"] == lays[0]["xz"]
+        assert lay["xz"] - lay["logits"] >= N * E * 4 + 256 * E * 4

@@ -7,9 +7,10 @@ import pytest
 import torch
 
 from oracle import rom_oracle as O
+from paper_2506_18145_amd import RomLayer
 from rom_synth import RomConfig, get_config, make_input, make_states, make_weights
 
-from gpu_util import TOL, check_routing, compare_layer, rel_err, run_layer, to_np
+from gpu_util import MARGIN, TOL, check_routing, compare_layer, rel_err, run_layer, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -107,6 +108,50 @@ def test_segmented_pipeline_is_deterministic_and_matches_unsegmented_routing():
         assert np.array_equal(base[name], seg1[name])
     assert np.array_equal(seg1["out"], seg2["out"])
     assert rel_err(seg1["out"], base["out"]) <= TOL["bf16"] * 0.25
+
+
+@pytest.mark.parametrize("name,over", [
+    ("cfg0", {}), ("cfg1", {}), ("cfg2", {}), ("cfg3", {}),
+    ("cfg1", dict(n_experts=5, top_k=3, batch=1, seq_len=777, d_model=128, d_inner=64, dt_rank=8, cfg_id=81)),
+    ("cfg1", dict(n_experts=64, top_k=8, batch=3, seq_len=1000, d_model=128, d_inner=64, dt_rank=8, cfg_id=82)),
+    ("cfg1", dict(n_experts=1, top_k=1, batch=1, seq_len=3, d_model=128, d_inner=64, dt_rank=8, cfg_id=83)),
+    ("cfg3", dict(n_experts=33, top_k=2, router_bias=None, batch=1, seq_len=70001, d_model=64, d_inner=64,
+                  dt_rank=8, cfg_id=84)),
+])
+def test_balance_stats(name, over):
+    """Eq. (16): F, mean router probability and the per-layer loss term from rom_balance_stats
+    against the oracle, fed by rom_route's own logits and counts.  F is exact up to fp32 rounding
+    of the division wherever the routing decision is (tokens inside the tie margin may move);
+    the means are fp32 sums of fp32 softmax values in a fixed order."""
+    cfg = get_config(name, **over)
+    w = make_weights(cfg)
+    x = make_input(cfg)
+    layer = RomLayer(cfg, w)
+    xd = layer.to_device(x.reshape(-1, cfg.d_model))
+    r = layer.route(xd)
+    alpha = 1e-3
+    frac, mean_prob, loss = layer.balance_stats(r["logits"], r["counts"], alpha)
+    frac2, mean_prob2, loss2 = layer.balance_stats(r["logits"], r["counts"], alpha)
+    torch.cuda.synchronize()
+    assert torch.equal(mean_prob, mean_prob2) and torch.equal(loss, loss2) and torch.equal(frac, frac2)
+    N, K, E = cfg.batch * cfg.seq_len, cfg.top_k, cfg.n_experts
+    logits = O.router_logits(x.reshape(-1, cfg.d_model), w["w_router"], w["b_router"])
+    idx = O.topk_select(logits, K)
+    o_frac, o_mean, o_loss = O.balance_stats(logits, idx, E, alpha)
+    n_close = int(np.count_nonzero(O.topk_margin(logits, K) < MARGIN))
+    f_tol = (n_close * K) / float(N * K) + 2e-7
+    assert np.max(np.abs(frac.cpu().numpy() - o_frac)) <= f_tol
+    assert np.max(np.abs(mean_prob.cpu().numpy() - o_mean)) <= 1e-5 * np.max(o_mean)
+    assert abs(float(loss.cpu()[0]) - o_loss) <= alpha * E * f_tol + 1e-5 * o_loss
+    assert abs(float(frac.sum().cpu()) - 1.0) < 1e-5 and abs(float(mean_prob.sum().cpu()) - 1.0) < 1e-5
+    # the same statistics from the logits and counts a forward call leaves in its workspace
+    if N <= 20000:
+        B, L = cfg.batch, cfg.seq_len
+        layer.forward(layer.to_device(x))
+        f3, p3, l3 = layer.balance_stats(layer.ws_view("logits", B, L), layer.ws_view("counts", B, L), alpha)
+        torch.cuda.synchronize()
+        assert torch.equal(f3, frac) and torch.equal(p3, mean_prob) and torch.equal(l3, loss)
+        assert torch.equal(layer.ws_view("expert_idx", B, L), r["expert_idx"])   # nothing clobbered
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
