@@ -27,6 +27,8 @@ Readings of the paper taken here (each is also listed in the design notes):
     are indicator sums like Eq. (11); dt_bias is one shared vector.
   * Top-K picks on logits, descending, lowest expert index on ties.
   * Eq. (16): per-layer term, F normalised by N*K, expectation over the call's tokens.
+  * The pre-norm is RMSNorm with a learned scale and an eps inside the square root (the
+    paper cites it without a formula or an eps); the skip adds the block's own input.
 """
 from __future__ import annotations
 
@@ -288,3 +290,46 @@ def rom_step(x, w, top_k, gate_mode, conv_state, ssm_state, expert_idx=None):
                             conv_state, ssm_state, expert_idx)
     res["out"] = res["out"][:, 0, :]
     return res
+
+
+# --------------------------------------------------------------------------
+# Pre-norm residual block and a stack of blocks (appendix, architectures overview)
+# --------------------------------------------------------------------------
+def rms_norm(x, weight, eps):
+    """Root-mean-square layer normalisation over the last axis:
+    x / sqrt(mean(x^2) + eps) * weight (the pre-norm the paper cites for every layer)."""
+    x = np.asarray(x, F64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * np.asarray(weight, F64)
+
+
+def rom_block_forward(x, w, top_k, gate_mode=0, eps=1e-5, conv_state=None, ssm_state=None,
+                      expert_idx=None):
+    """out = x + RoM(RMSNorm(x)): the pre-norm, skip-connected layer of the appendix's
+    architecture overview.  w["norm_w"] [D_m] is the norm's scale.  Returns the dict of
+    rom_layer_forward (intermediates of the inner layer) with "out" the block output and
+    "xn" the normalised input."""
+    x = np.asarray(x, F64)
+    xn = rms_norm(x, w["norm_w"], eps)
+    res = rom_layer_forward(xn, w, top_k, gate_mode, conv_state, ssm_state, expert_idx)
+    res["xn"] = xn
+    res["branch"] = res["out"]
+    res["out"] = x + res["out"]
+    return res
+
+
+def rom_stack_forward(x, layers, top_k, gate_mode=0, eps=1e-5, conv_states=None, ssm_states=None,
+                      expert_idx=None):
+    """Blocks applied one after another: layer j reads layer j-1's output.  conv_states /
+    ssm_states: per-layer lists (or None for zeros); expert_idx: per-layer list (or None).
+    Returns (out, per-layer result dicts)."""
+    h = np.asarray(x, F64)
+    results = []
+    for j, w in enumerate(layers):
+        res = rom_block_forward(h, w, top_k, gate_mode, eps,
+                                None if conv_states is None else conv_states[j],
+                                None if ssm_states is None else ssm_states[j],
+                                None if expert_idx is None else expert_idx[j])
+        results.append(res)
+        h = res["out"]
+    return h, results

@@ -498,6 +498,79 @@ def test_state_api_split_and_step():
     assert np.allclose(st["ssm_state"], h, rtol=1e-12)
 
 
+def test_rms_norm_against_library_and_closed_forms():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((3, 7, 24)) * 3.0
+    wn = rng.uniform(0.5, 1.5, 24)
+    ref = F.rms_norm(torch.from_numpy(x), (24,), torch.from_numpy(wn), eps=1e-5).numpy()
+    np.testing.assert_allclose(O.rms_norm(x, wn, 1e-5), ref, rtol=1e-13, atol=1e-14)
+    # a constant row c maps to sign(c) * w / sqrt(1 + eps / c^2)
+    np.testing.assert_allclose(O.rms_norm(np.full((1, 24), -2.0), wn, 0.04)[0], -wn / np.sqrt(1.01), rtol=1e-14)
+    # eps = 0: unit RMS for w = 1 and invariance to the input's scale
+    y = O.rms_norm(x, np.ones(24), 0.0)
+    np.testing.assert_allclose(np.sqrt(np.mean(y * y, axis=-1)), 1.0, rtol=1e-14)
+    np.testing.assert_allclose(O.rms_norm(7.5 * x, wn, 0.0), O.rms_norm(x, wn, 0.0), rtol=1e-13)
+    # rows are independent, and it is the row that is normalised (not the column)
+    np.testing.assert_allclose(O.rms_norm(x[1:2, 3:4], wn, 1e-5), O.rms_norm(x, wn, 1e-5)[1:2, 3:4], rtol=1e-14)
+
+
+def test_block_is_skip_plus_layer_of_normalised_input():
+    """The block against its parts assembled from library routines: torch's rms_norm in front of
+    a dense Mamba layer (E = 1), plus the input; with W_out = 0 the block is the identity; and
+    a routed block keeps the router's view of the *normalised* input."""
+    cfg = tiny_cfg(n_experts=1)
+    w = _weights(cfg)
+    w["norm_w"] = np.random.default_rng(8).uniform(0.5, 1.5, cfg.d_model).astype(np.float32)
+    x = make_input(cfg).astype(np.float64) * 2.5
+    xn = F.rms_norm(torch.from_numpy(x), (cfg.d_model,), torch.from_numpy(w["norm_w"]).double(), eps=1e-5)
+    want = x + _dense_mamba_torch(xn.numpy(), w)
+    got = O.rom_block_forward(x, w, 1, 0, 1e-5)
+    np.testing.assert_allclose(got["out"], want, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(got["out"] - got["branch"], x, rtol=0, atol=1e-12)
+
+    w0 = dict(w)
+    w0["w_out"] = np.zeros_like(w["w_out"])
+    np.testing.assert_array_equal(O.rom_block_forward(x, w0, 1, 0, 1e-5)["out"], x)
+
+    cfg = tiny_cfg(n_experts=4, top_k=2)
+    w = _weights(cfg, 3)
+    w["norm_w"] = np.random.default_rng(9).uniform(0.5, 1.5, cfg.d_model).astype(np.float32)
+    x = make_input(cfg).astype(np.float64)
+    blk = O.rom_block_forward(x, w, 2, 1, 1e-5)
+    inner = O.rom_layer_forward(O.rms_norm(x, w["norm_w"], 1e-5), w, 2, 1)
+    assert blk["expert_idx"].tolist() == inner["expert_idx"].tolist()
+    # scaling the block input by a positive constant leaves the branch (almost: eps) unchanged
+    blk2 = O.rom_block_forward(1000.0 * x, w, 2, 1, 0.0)
+    blk1 = O.rom_block_forward(x, w, 2, 1, 0.0)
+    np.testing.assert_allclose(blk2["branch"], blk1["branch"], rtol=1e-9, atol=1e-12)
+
+
+def test_stack_is_the_composition_of_blocks_with_per_layer_state():
+    cfg = tiny_cfg(n_experts=3, top_k=1)
+    layers = []
+    for j in range(3):
+        w = _weights(cfg, 10 + j)
+        w["norm_w"] = np.random.default_rng(20 + j).uniform(0.5, 1.5, cfg.d_model).astype(np.float32)
+        layers.append(w)
+    x = make_input(cfg).astype(np.float64)
+    out, res = O.rom_stack_forward(x, layers, 1, 0, 1e-5)
+    h = x
+    for j in range(3):
+        h = h + O.rom_layer_forward(O.rms_norm(h, layers[j]["norm_w"], 1e-5), layers[j], 1, 0)["out"]
+    np.testing.assert_allclose(out, h, rtol=1e-12, atol=1e-13)
+    # prefill of a prefix, then the rest from the per-layer states, equals the unsplit run
+    cut = 5
+    o1, r1 = O.rom_stack_forward(x[:, :cut], layers, 1, 0, 1e-5)
+    o2, _ = O.rom_stack_forward(x[:, cut:], layers, 1, 0, 1e-5, [r["conv_state"] for r in r1],
+                                [r["ssm_state"] for r in r1])
+    np.testing.assert_allclose(np.concatenate([o1, o2], axis=1), out, rtol=1e-10, atol=1e-12)
+    # causal through the whole stack
+    x2 = x.copy()
+    x2[:, 6:] += 1.0
+    out2, _ = O.rom_stack_forward(x2, layers, 1, 0, 1e-5)
+    np.testing.assert_array_equal(out2[:, :6], out[:, :6])
+
+
 def test_softplus_and_silu_against_library():
     v = np.linspace(-40, 40, 161)
     assert np.allclose(O.softplus(v), F.softplus(torch.from_numpy(v), threshold=1e9).numpy(), rtol=1e-13)
