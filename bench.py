@@ -101,6 +101,65 @@ def decode_step_rate(n_steps=512):
             "frac": (w_bytes + s_bytes) / (dt / n_steps) / 1e9 / PEAK_HBM_GBS}
 
 
+def device_weights(cfg, seed):
+    """One layer's parameters drawn on the GPU (same shapes and distributions as
+    rom_synth.make_weights; a 48-layer stack would take minutes to draw on the host)."""
+    import math
+    import torch
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(seed)
+    E, Ex = cfg.n_experts, cfg.n_experts_xdt
+    Dm, De, Ds, k, R = cfg.d_model, cfg.d_inner, cfg.d_state, cfg.d_conv, cfg.dt_rank
+    t = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+
+    def normal(shape, std):
+        return (torch.randn(shape, generator=g, device="cuda:0", dtype=torch.float32) * std).to(t)
+
+    def uniform(shape, lo, hi):
+        return torch.rand(shape, generator=g, device="cuda:0", dtype=torch.float32) * (hi - lo) + lo
+
+    lim = 1.0 / math.sqrt(k)
+    tau = torch.exp(uniform((De,), math.log(1e-3), math.log(1e-1)))
+    return {
+        "w_router": normal((E, Dm), 0.02), "b_router": None,
+        "w_in": normal((E, 2 * De, Dm), cfg.weight_std),
+        "conv_w": uniform((De, k), -lim, lim), "conv_b": uniform((De,), -lim, lim),
+        "w_x": normal((Ex, R + 2 * Ds, De), cfg.weight_std), "w_dt": normal((Ex, De, R), cfg.weight_std),
+        "dt_bias": tau + torch.log(-torch.expm1(-tau)),
+        "A_log": torch.log(torch.arange(1, Ds + 1, device="cuda:0", dtype=torch.float32)).repeat(De, 1),
+        "D": torch.ones(De, device="cuda:0"), "w_out": normal((E, Dm, De), cfg.weight_std),
+        "norm_w": torch.ones(Dm, device="cuda:0"),
+    }
+
+
+def stack_rate(cfg, n_layers, steps, warmup):
+    """n_layers pre-norm residual blocks of the workload's shape (the paper's 1.3B-active model is 48
+    layers of d_model 2048), one rom_stack_forward call per step; embedding and output head are
+    not part of it.  Every layer has its own weights, so nothing is served from a cache."""
+    import torch
+    from paper_2506_18145_amd import RomLayer, RomStack
+    from rom_synth import make_input
+    layers = [RomLayer(cfg, device_weights(cfg, 7000 + j), device="cuda:0") for j in range(n_layers)]
+    stack = RomStack(layers, eps=1e-5, fold_in_place=True)
+    x = layers[0].to_device(make_input(cfg))
+    out = torch.empty_like(x)
+    for _ in range(warmup):
+        stack.forward(x, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        stack.forward(x, out=out)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    finite = bool(torch.isfinite(out.float()).all().item())
+    n_tok = cfg.batch * cfg.seq_len
+    w_bytes = sum(v.numel() * v.element_size() for ly in layers for v in ly.weights.values() if v is not None)
+    return {"workload": f"{n_layers} blocks (RMSNorm + RoM layer + skip) of {cfg.name}'s shape, one sequence of "
+                        f"{cfg.seq_len} tokens", "n_layers": n_layers, "ms_per_forward": dt * 1e3,
+            "ms_per_layer": dt * 1e3 / n_layers, "tokens_per_s": n_tok / dt, "weights_gib": w_bytes / 2 ** 30,
+            "output_finite": finite}
+
+
 def time_forward(cfg, steps, warmup, calibrate_copy=False):
     """K timed calls of rom_layer_forward on resident inputs.  Returns (ms per call, ms per call
     without the stage events, per-stage dict)."""
@@ -196,6 +255,8 @@ def main():
                     help="skip the extra rom_step measurement (256 sequences x 512 steps, cfg4)")
     ap.add_argument("--no-shared-xdt", action="store_true",
                     help="skip the extra measurement of the shared x/dt variant of the workload")
+    ap.add_argument("--stack-layers", type=int, default=48,
+                    help="layers of the extra whole-stack measurement (0 = skip it)")
     ap.add_argument("--only-step", action="store_true",
                     help="run only the rom_step measurement and print its JSON object (for profiling)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -250,6 +311,8 @@ def main():
             "workload": f"{cfg.name} with one shared x/dt projection (E_x = 1)", "ms_per_step": ms_s,
             "tokens_per_s": n_tok / (ms_s * 1e-3),
             "stages_ms": {k: v["ms"] for k, v in stages_s.items()}}
+    if args.stack_layers > 0:
+        result["stack_forward"] = stack_rate(cfg, args.stack_layers, 3, 1)
     if not args.no_step:
         result["decode_step"] = decode_step_rate()
     if not args.no_cpu_baseline:

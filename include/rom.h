@@ -141,9 +141,11 @@ ROM_API int rom_route(const rom_dims *dims, const rom_weights *w, const void *x,
  *                          workspace region rom_ws_layout.logits (N = B * L)
  *   counts     i32 [E]     as written by rom_route, or the workspace region rom_ws_layout.counts
  *   frac, mean_prob  f32 [E]  out;  loss  f32 [1]  out   (all device pointers)
- *   ws/ws_bytes  workspace of at least rom_workspace_bytes(dims, N, 1).  It may be the workspace
- *                the logits and counts live in: the scratch this call uses lies at the same offset
- *                for every (B, L) with B * L = N and overlaps no region named in rom_ws_layout.
+ *   ws/ws_bytes  a workspace that is large enough for a forward call over these N tokens
+ *                (rom_workspace_bytes(dims, B, L) for any B * L = N; only its first part, up to
+ *                rom_ws_layout.xz, is needed).  It may be the workspace the logits and counts
+ *                live in: the scratch this call uses lies at the same offset for every such
+ *                (B, L) and overlaps no region named in rom_ws_layout.
  * The sums are taken in a fixed order: repeated calls give identical bits.
  * N <= 0 is ROM_E_INVAL (the mean over no tokens is undefined). */
 ROM_API int rom_balance_stats(const rom_dims *dims, const float *logits, const int32_t *counts,
@@ -169,6 +171,66 @@ ROM_API int rom_layer_forward(const rom_dims *dims, const rom_weights *w, const 
 ROM_API int rom_step(const rom_dims *dims, const rom_weights *w, const void *x, int64_t B,
              float *conv_state, float *ssm_state, void *out,
              void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ---- Pre-norm residual block (appendix, architectures overview: every layer sits behind a
+ * pre-norm and a skip connection):   out = x + RoM(RMSNorm(x)),
+ *   RMSNorm(x)[n, :] = x[n, :] / sqrt(mean_d(x[n, d]^2) + eps) * norm_weight[:].
+ * The norm is never materialised.  The router kernel accumulates each token's sum of squares
+ * while it reads x for the logits and applies norm_weight itself; the in projection runs on the
+ * raw x with a weight whose columns were pre-multiplied by norm_weight (rom_fold_norm, once per
+ * weight load) and scales every output row by the token's 1/rms in its epilogue; the skip is
+ * added where the out projection (K == 1) or the combine (K > 1) writes out.
+ * The block calls below therefore expect w->w_in to be the FOLDED weight; all other members of
+ * rom_weights are the plain ones. */
+
+/* w_in_folded[e, o, d] = w_in[e, o, d] * norm_weight[d], rounded once to T.
+ *   w_in, w_in_folded  T [E, 2*d_inner, d_model] (device); may be the same buffer
+ *   norm_weight        f32 [d_model] (device) */
+ROM_API int rom_fold_norm(const rom_dims *dims, const void *w_in, const float *norm_weight,
+                  void *w_in_folded, void *hip_stream);
+
+/* One block: arguments as rom_layer_forward plus
+ *   norm_weight  f32 [d_model] (device, 16-byte aligned), eps >= 0
+ * out must not alias x (x is read again for the skip).  Workspace: rom_workspace_bytes(dims, B, L).
+ * The intermediates named in rom_ws_layout are those of the inner layer (xz is the projection
+ * of the normalised input). */
+ROM_API int rom_block_forward(const rom_dims *dims, const rom_weights *w, const float *norm_weight,
+                      float eps, const void *x, int64_t B, int64_t L,
+                      const float *conv_state_in, const float *ssm_state_in,
+                      void *out, float *conv_state_out, float *ssm_state_out,
+                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/* One new token per sequence through one block; states updated in place (see rom_step). */
+ROM_API int rom_block_step(const rom_dims *dims, const rom_weights *w, const float *norm_weight,
+                   float eps, const void *x, int64_t B, float *conv_state, float *ssm_state,
+                   void *out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* One block's parameters inside a stack (host struct; the pointers are device pointers). */
+typedef struct rom_block {
+  rom_weights  w;            /* w.w_in folded with norm_weight (rom_fold_norm) */
+  const float *norm_weight;  /* f32 [d_model] */
+} rom_block;
+
+/* n_layers blocks of the same shape, one after another: layer j reads layer j-1's output.
+ *   blocks        host array [n_layers]
+ *   x             T [B, L, d_model];  out  T [B, L, d_model], must not alias x
+ *   tmp           T [B, L, d_model] scratch (the layers write tmp and out in turn); may be
+ *                 NULL when n_layers == 1; must alias neither x nor out
+ *   conv_state_in / ssm_state_in    f32 [n_layers, B, d_inner, d_conv-1] / [n_layers, B, d_inner,
+ *                 d_state], or NULL (zeros); *_out likewise, written if not NULL (may alias *_in)
+ *   ws            one layer's workspace, rom_workspace_bytes(dims, B, L), reused by every layer
+ * Every block's pointers are checked before the first layer is launched. */
+ROM_API int rom_stack_forward(const rom_dims *dims, const rom_block *blocks, int n_layers, float eps,
+                      const void *x, int64_t B, int64_t L,
+                      const float *conv_state_in, const float *ssm_state_in,
+                      void *out, float *conv_state_out, float *ssm_state_out,
+                      void *tmp, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* One new token per sequence through the whole stack: x, out, tmp T [B, d_model]; the
+ * [n_layers, B, ...] states are updated in place. */
+ROM_API int rom_stack_step(const rom_dims *dims, const rom_block *blocks, int n_layers, float eps,
+                   const void *x, int64_t B, float *conv_state, float *ssm_state,
+                   void *out, void *tmp, void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Static description of an error code. */
 ROM_API const char *rom_strerror(int code);

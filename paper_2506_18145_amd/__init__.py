@@ -7,8 +7,14 @@ from .binding import (  # noqa: F401
     RomDims,
     RomError,
     RomLayer,
+    RomStack,
     load_library,
     rom_balance_stats,
+    rom_block_forward,
+    rom_block_step,
+    rom_fold_norm,
+    rom_stack_forward,
+    rom_stack_step,
     rom_layer_forward,
     rom_profile_collect,
     rom_profile_enable,

@@ -31,6 +31,10 @@ class _RomWeights(ctypes.Structure):
         "w_out")]
 
 
+class _RomBlock(ctypes.Structure):
+    _fields_ = [("w", _RomWeights), ("norm_weight", ctypes.c_void_p)]
+
+
 class _RomWsLayout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in (
         "total_bytes", "expert_idx", "gate", "counts", "offsets", "perm", "inv_perm", "logits", "xz",
@@ -61,6 +65,21 @@ def load_library() -> ctypes.CDLL:
                                       P, P, P, P, P, P, SZ, P]
     lib.rom_step.restype = ctypes.c_int
     lib.rom_step.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64, P, P, P, P, SZ, P]
+    F32 = ctypes.c_float
+    lib.rom_fold_norm.restype = ctypes.c_int
+    lib.rom_fold_norm.argtypes = [ctypes.POINTER(RomDims), P, P, P, P]
+    lib.rom_block_forward.restype = ctypes.c_int
+    lib.rom_block_forward.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, F32, P, I64,
+                                      I64, P, P, P, P, P, P, SZ, P]
+    lib.rom_block_step.restype = ctypes.c_int
+    lib.rom_block_step.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, F32, P, I64, P, P,
+                                   P, P, SZ, P]
+    lib.rom_stack_forward.restype = ctypes.c_int
+    lib.rom_stack_forward.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomBlock), ctypes.c_int, F32, P,
+                                      I64, I64, P, P, P, P, P, P, P, SZ, P]
+    lib.rom_stack_step.restype = ctypes.c_int
+    lib.rom_stack_step.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomBlock), ctypes.c_int, F32, P,
+                                   I64, P, P, P, P, P, SZ, P]
     lib.rom_strerror.restype = ctypes.c_char_p
     lib.rom_strerror.argtypes = [ctypes.c_int]
     lib.rom_profile_enable.restype = ctypes.c_int
@@ -143,6 +162,56 @@ def rom_step(dims, weights, x, B, conv_state, ssm_state, out, ws):
     _check(code, "rom_step")
 
 
+def _nbytes(t) -> int:
+    return t.numel() * t.element_size() if t is not None else 0
+
+
+def rom_fold_norm(dims, w_in, norm_weight, w_in_folded):
+    _check(load_library().rom_fold_norm(ctypes.byref(dims), _ptr(w_in), _ptr(norm_weight),
+                                        _ptr(w_in_folded), _stream()), "rom_fold_norm")
+
+
+def rom_block_forward(dims, weights, norm_weight, eps, x, B, L, conv_state_in, ssm_state_in, out,
+                      conv_state_out, ssm_state_out, ws):
+    code = load_library().rom_block_forward(
+        ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(norm_weight), eps, _ptr(x), B, L,
+        _ptr(conv_state_in), _ptr(ssm_state_in), _ptr(out), _ptr(conv_state_out), _ptr(ssm_state_out),
+        _ptr(ws), _nbytes(ws), _stream())
+    _check(code, "rom_block_forward")
+
+
+def rom_block_step(dims, weights, norm_weight, eps, x, B, conv_state, ssm_state, out, ws):
+    code = load_library().rom_block_step(
+        ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(norm_weight), eps, _ptr(x), B,
+        _ptr(conv_state), _ptr(ssm_state), _ptr(out), _ptr(ws), _nbytes(ws), _stream())
+    _check(code, "rom_block_step")
+
+
+def make_blocks(layers):
+    """Host array of rom_block for a list of (weights dict with folded w_in, norm_weight) pairs."""
+    arr = (_RomBlock * len(layers))()
+    for j, (w, norm_weight) in enumerate(layers):
+        arr[j].w = _weights_struct(w)
+        arr[j].norm_weight = _ptr(norm_weight)
+    return arr
+
+
+def rom_stack_forward(dims, blocks, eps, x, B, L, conv_state_in, ssm_state_in, out, conv_state_out,
+                      ssm_state_out, tmp, ws):
+    code = load_library().rom_stack_forward(
+        ctypes.byref(dims), blocks, len(blocks), eps, _ptr(x), B, L, _ptr(conv_state_in),
+        _ptr(ssm_state_in), _ptr(out), _ptr(conv_state_out), _ptr(ssm_state_out), _ptr(tmp), _ptr(ws),
+        _nbytes(ws), _stream())
+    _check(code, "rom_stack_forward")
+
+
+def rom_stack_step(dims, blocks, eps, x, B, conv_state, ssm_state, out, tmp, ws):
+    code = load_library().rom_stack_step(
+        ctypes.byref(dims), blocks, len(blocks), eps, _ptr(x), B, _ptr(conv_state), _ptr(ssm_state),
+        _ptr(out), _ptr(tmp), _ptr(ws), _nbytes(ws), _stream())
+    _check(code, "rom_stack_step")
+
+
 def rom_set_segments(n_segments: int) -> None:
     _check(load_library().rom_set_segments(n_segments), "rom_set_segments")
 
@@ -179,10 +248,46 @@ class RomLayer:
             if arr is None:
                 self.weights[name] = None
                 continue
-            t = torch.from_numpy(arr)
+            t = arr if isinstance(arr, torch.Tensor) else torch.from_numpy(arr)   # host arrays or tensors
             t = t.to(self.tdtype) if name in typed else t.to(torch.float32)
             self.weights[name] = t.to(self.device).contiguous()
         self._ws: Optional[torch.Tensor] = None
+        self._block_weights: Optional[Dict[str, Optional[torch.Tensor]]] = None
+
+    def block_weights(self, in_place: bool = False) -> Dict[str, Optional[torch.Tensor]]:
+        """The parameters the block entry points take: w_in with the pre-norm's scale folded in
+        (rom_fold_norm), everything else shared with the plain layer.  in_place overwrites w_in
+        (the plain layer calls are then no longer meaningful) instead of keeping a second copy."""
+        if self._block_weights is None:
+            if self.weights.get("norm_w") is None:
+                raise RomError("this layer has no norm_w")
+            folded = self.weights["w_in"] if in_place else torch.empty_like(self.weights["w_in"])
+            rom_fold_norm(self.dims, self.weights["w_in"], self.weights["norm_w"], folded)
+            self._block_weights = dict(self.weights)
+            self._block_weights["w_in"] = folded
+        return self._block_weights
+
+    def block_forward(self, x: torch.Tensor, conv_state=None, ssm_state=None, return_states=False,
+                      eps: float = 1e-5):
+        B, L, _ = x.shape
+        out = torch.empty_like(x)
+        conv_out = ssm_out = None
+        if return_states:
+            f32 = dict(dtype=torch.float32, device=self.device)
+            conv_out = torch.empty((B, self.dims.d_inner, self.dims.d_conv - 1), **f32)
+            ssm_out = torch.empty((B, self.dims.d_inner, self.dims.d_state), **f32)
+        rom_block_forward(self.dims, self.block_weights(), self.weights["norm_w"], eps, x, B, L, conv_state,
+                          ssm_state, out, conv_out, ssm_out, self.workspace(max(B, 1), max(L, 1)))
+        return (out, conv_out, ssm_out) if return_states else out
+
+    def block_step(self, x: torch.Tensor, conv_state: torch.Tensor, ssm_state: torch.Tensor,
+                   out: Optional[torch.Tensor] = None, eps: float = 1e-5):
+        B = x.shape[0]
+        if out is None:
+            out = torch.empty_like(x)
+        rom_block_step(self.dims, self.block_weights(), self.weights["norm_w"], eps, x, B, conv_state,
+                       ssm_state, out, self.workspace(max(B, 1), 1))
+        return out
 
     def to_device(self, arr, typed=True) -> torch.Tensor:
         t = torch.from_numpy(arr)
@@ -263,4 +368,53 @@ class RomLayer:
         if out is None:
             out = torch.empty_like(x)
         rom_step(self.dims, self.weights, x, B, conv_state, ssm_state, out, self.workspace(max(B, 1), 1))
+        return out
+
+
+class RomStack:
+    """n_layers pre-norm residual blocks of one shape behind rom_stack_forward / rom_stack_step."""
+
+    def __init__(self, layers, eps: float = 1e-5, fold_in_place: bool = True):
+        if not layers:
+            raise RomError("a stack needs at least one layer")
+        self.layers = list(layers)
+        self.dims = self.layers[0].dims
+        self.device = self.layers[0].device
+        self.eps = eps
+        self._keep = [(ly.block_weights(in_place=fold_in_place), ly.weights["norm_w"]) for ly in self.layers]
+        self.blocks = make_blocks(self._keep)
+        self._tmp: Optional[torch.Tensor] = None
+
+    def _scratch(self, like: torch.Tensor) -> Optional[torch.Tensor]:
+        if len(self.layers) == 1:
+            return None
+        if self._tmp is None or self._tmp.shape != like.shape or self._tmp.dtype != like.dtype:
+            self._tmp = torch.empty_like(like)
+        return self._tmp
+
+    def state_shapes(self, B: int):
+        n, d = len(self.layers), self.dims
+        return (n, B, d.d_inner, d.d_conv - 1), (n, B, d.d_inner, d.d_state)
+
+    def forward(self, x: torch.Tensor, conv_state=None, ssm_state=None, return_states=False,
+                out: Optional[torch.Tensor] = None):
+        B, L, _ = x.shape
+        if out is None:
+            out = torch.empty_like(x)
+        conv_out = ssm_out = None
+        if return_states:
+            cs, ss = self.state_shapes(B)
+            conv_out = torch.empty(cs, dtype=torch.float32, device=self.device)
+            ssm_out = torch.empty(ss, dtype=torch.float32, device=self.device)
+        rom_stack_forward(self.dims, self.blocks, self.eps, x, B, L, conv_state, ssm_state, out, conv_out,
+                          ssm_out, self._scratch(x), self.layers[0].workspace(max(B, 1), max(L, 1)))
+        return (out, conv_out, ssm_out) if return_states else out
+
+    def step(self, x: torch.Tensor, conv_state: torch.Tensor, ssm_state: torch.Tensor,
+             out: Optional[torch.Tensor] = None):
+        B = x.shape[0]
+        if out is None:
+            out = torch.empty_like(x)
+        rom_stack_step(self.dims, self.blocks, self.eps, x, B, conv_state, ssm_state, out, self._scratch(x),
+                       self.layers[0].workspace(max(B, 1), 1))
         return out

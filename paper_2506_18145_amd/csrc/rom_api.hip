@@ -64,6 +64,7 @@ struct Plan {                 // byte offsets inside the workspace
   size_t xz, xz_sorted, u, xdbl, dt_low, bc, dt, dt_raw, g, op_sorted, conv_tmp;
   size_t seg_lo, seg_hi, conv_carry, ssm_carry;
   size_t scan_q[kMaxSegments], scan_p[kMaxSegments];
+  size_t rstd;                // f32 [N]: 1 / rms of every token of a pre-norm block's input
   int xproj_slices;           // inner-dimension slices the xdbl buffer has room for
 };
 
@@ -154,6 +155,7 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
     p.scan_q[i] = take(bytes);
     p.scan_p[i] = take(bytes);
   }
+  p.rstd = take(N * 4);
   p.total = off;
   return p;
 }
@@ -240,6 +242,15 @@ __global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict
   if (i < n) dst[i] = src[i];
 }
 
+// dst[r, d] = src[r, d] * scale[d]  (rows of length n_cols; dst may be src)
+template <typename T>
+__global__ void fold_cols_kernel(const T *src, const float *__restrict__ scale, T *dst, int64_t n_rows,
+                                 int n_cols) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i >= n_rows * n_cols) return;
+  dst[i] = from_f32<T>(to_f32(src[i]) * scale[i % n_cols]);
+}
+
 struct SegTok {
   int64_t t[kMaxSegments + 1];
 };
@@ -266,13 +277,21 @@ __global__ void segment_bounds_kernel(const int32_t *__restrict__ offsets, const
   seg_hi[i] = res[1];
 }
 
+// What turns the layer into the pre-norm, skip-connected block: RMSNorm in front (its scale is
+// folded into w_in by rom_fold_norm; the router applies it itself), the block input added behind.
+struct BlockOpts {
+  const float *norm_w;   // f32 [d_model]
+  float eps;
+};
+
 int route_into(const rom_dims *d, const rom_weights *w, const void *x, int64_t n_tok,
                int32_t *expert_idx, float *gate, int32_t *counts, int32_t *offsets, int32_t *perm,
                int32_t *inv_perm, int32_t *tok_of_pos, int32_t *block_counts, float *logits,
-               hipStream_t s, StageMark *mark) {
+               const BlockOpts *blk, float *rstd, hipStream_t s, StageMark *mark) {
   if (mark) mark->begin(0, ROM_STAGE_ROUTE, s);
   ROM_TRY(launch_route_topk(d->dtype, x, w->w_router, w->b_router, n_tok, d->d_model, d->n_experts,
-                            d->top_k, d->gate_mode, expert_idx, gate, logits, s));
+                            d->top_k, d->gate_mode, expert_idx, gate, logits, blk ? blk->norm_w : nullptr,
+                            blk ? blk->eps : 0.0f, rstd, s));
   if (mark) mark->end(0, ROM_STAGE_ROUTE, s);
   if (mark) mark->begin(0, ROM_STAGE_PERMUTE, s);
   ROM_TRY(launch_permutation(expert_idx, n_tok * d->top_k, d->n_experts, d->top_k, block_counts,
@@ -283,11 +302,12 @@ int route_into(const rom_dims *d, const rom_weights *w, const void *x, int64_t n
 
 int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t B, int64_t L,
                  const float *conv_in, const float *ssm_in, void *out, float *conv_out,
-                 float *ssm_out, void *ws, size_t ws_bytes, hipStream_t s) {
+                 float *ssm_out, void *ws, size_t ws_bytes, hipStream_t s, const BlockOpts *blk = nullptr) {
   int rc = check_dims(d);
   if (rc != ROM_OK) return rc;
   rc = check_weights(d, w);
   if (rc != ROM_OK) return rc;
+  if (blk && (!blk->norm_w || !aligned16(blk->norm_w) || !(blk->eps >= 0.0f))) return ROM_E_INVAL;
   if (B < 0 || L < 0) return ROM_E_INVAL;
   if (B == 0 || L == 0) return ROM_OK;
   if (!x || !out || !ws || x == out) return ROM_E_INVAL;
@@ -315,12 +335,13 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   int32_t *seg_lo = reinterpret_cast<int32_t *>(at(p.seg_lo));
   int32_t *seg_hi = reinterpret_cast<int32_t *>(at(p.seg_hi));
   const size_t eb = d->dtype == ROM_DTYPE_BF16 ? 2 : 4;
+  const float *rstd = blk ? reinterpret_cast<const float *>(at(p.rstd)) : nullptr;
 
   StageMark mark(sg.n == 1);
   rc = route_into(d, w, x, N, reinterpret_cast<int32_t *>(at(p.expert_idx)), gate,
                   reinterpret_cast<int32_t *>(at(p.counts)), offsets, reinterpret_cast<int32_t *>(at(p.perm)),
                   inv_perm, tok_of_pos, reinterpret_cast<int32_t *>(at(p.block_counts)),
-                  reinterpret_cast<float *>(at(p.logits)), s, &mark);
+                  reinterpret_cast<float *>(at(p.logits)), blk, reinterpret_cast<float *>(at(p.rstd)), s, &mark);
   if (rc != ROM_OK) return rc;
   if (sg.n > 1) {
     SegTok st;
@@ -364,10 +385,12 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
     ga.W = w->w_in; ga.N = 2 * De; ga.K = Dm;
     routed(ga);
     ga.C = multi ? at(p.xz_sorted) : at(p.xz); ga.ldc = 2 * De; ga.c_rows = multi ? nullptr : tok_of_pos;
+    // pre-norm block: x @ (W . norm_w)^T scaled by the token's 1/rms is RMSNorm(x) @ W^T
+    if (!multi) ga.row_scale = rstd;
     ROM_TRY(launch_grouped_gemm(ga, st));
     if (multi)
       ROM_TRY(launch_slot_sum(eb == 4, eb == 4, at(p.xz_sorted), 2 * De, at(p.xz) + tok0 * 2 * De * eb, 2 * De,
-                              inv_perm + tok0 * K, n_tok, K, 2 * De, nullptr, 0, st));
+                              inv_perm + tok0 * K, n_tok, K, 2 * De, nullptr, 0, rstd ? rstd + tok0 : nullptr, st));
     mark.end(sgi, ROM_STAGE_IN_PROJ, st);
 
     // short conv + SiLU, Eq. (2).  A time segment takes the three rows before it from the
@@ -440,7 +463,7 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
       ga.C = at(p.dt_raw);     // one expert's output per slot, stored in T as in_proj's; summed in fp32 below
       ROM_TRY(launch_grouped_gemm(ga, st));
       ROM_TRY(launch_slot_sum(eb == 4, eb == 4, at(p.dt_raw), De, at(p.dt) + tok0 * De * eb, De, inv_perm + tok0 * K,
-                              n_tok, K, De, w->dt_bias, 1, st));
+                              n_tok, K, De, w->dt_bias, 1, nullptr, st));
     } else {
       if (routed_xdt) {
         ga.A = at(p.dt_low); ga.a_rows = tok_of_pos; ga.C = at(p.dt); ga.c_rows = tok_of_pos;
@@ -490,10 +513,12 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
       mark.end(sgi, ROM_STAGE_OUT_PROJ, st);
       mark.begin(sgi, ROM_STAGE_COMBINE, st);
       ROM_TRY(launch_combine(d->dtype, at(p.op_sorted), inv_perm + tok0 * K, gate + tok0 * K,
-                             static_cast<char *>(out) + tok0 * Dm * eb, n_tok, K, Dm, st));
+                             static_cast<char *>(out) + tok0 * Dm * eb, n_tok, K, Dm,
+                             blk ? static_cast<const char *>(x) + tok0 * Dm * eb : nullptr, st));
       mark.end(sgi, ROM_STAGE_COMBINE, st);
     } else {
       ga.C = out; ga.ldc = Dm; ga.c_rows = tok_of_pos; ga.row_scale = gate;   // gate[n*1 + 0]
+      if (blk) ga.residual = x;                                               // skip connection
       ROM_TRY(launch_grouped_gemm(ga, st));
       mark.end(sgi, ROM_STAGE_OUT_PROJ, st);
     }
@@ -556,7 +581,7 @@ int rom_route(const rom_dims *dims, const rom_weights *w, const void *x, int64_t
   char *base = static_cast<char *>(ws);
   return route_into(dims, w, x, N, expert_idx, gate, counts, offsets, perm, inv_perm,
                     reinterpret_cast<int32_t *>(base + p.tok_of_pos),
-                    reinterpret_cast<int32_t *>(base + p.block_counts), logits,
+                    reinterpret_cast<int32_t *>(base + p.block_counts), logits, nullptr, nullptr,
                     static_cast<hipStream_t>(hip_stream), nullptr);
 }
 
@@ -568,8 +593,9 @@ int rom_balance_stats(const rom_dims *dims, const float *logits, const int32_t *
   if (N <= 0 || !logits || !counts || !frac || !mean_prob || !loss || !ws) return ROM_E_INVAL;
   if ((reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return ROM_E_INVAL;
   if (N * dims->top_k > (1ll << 30)) return ROM_E_UNSUPPORTED;
+  // the scratch lies in front of every region whose size depends on how N splits into B x L
   Plan p = make_plan(dims, N, 1);
-  if (ws_bytes < p.total) return ROM_E_WORKSPACE;
+  if (ws_bytes < p.balance_part + balance_scratch_bytes(dims->n_experts)) return ROM_E_WORKSPACE;
   float *partial = reinterpret_cast<float *>(static_cast<char *>(ws) + p.balance_part);
   return launch_balance_stats(logits, counts, N, dims->n_experts, dims->top_k, alpha, partial, frac,
                               mean_prob, loss, static_cast<hipStream_t>(hip_stream)) == hipSuccess
@@ -583,6 +609,81 @@ int rom_layer_forward(const rom_dims *dims, const rom_weights *w, const void *x,
                       void *hip_stream) {
   return forward_impl(dims, w, x, B, L, conv_state_in, ssm_state_in, out, conv_state_out,
                       ssm_state_out, ws, ws_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int rom_fold_norm(const rom_dims *dims, const void *w_in, const float *norm_weight, void *w_in_folded,
+                  void *hip_stream) {
+  int rc = check_dims(dims);
+  if (rc != ROM_OK) return rc;
+  if (!w_in || !norm_weight || !w_in_folded) return ROM_E_INVAL;
+  const int64_t rows = static_cast<int64_t>(dims->n_experts) * 2 * dims->d_inner;
+  const int64_t n = rows * dims->d_model;
+  const dim3 grid(static_cast<unsigned>(ceil_div(n, 256)));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (dims->dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL(fold_cols_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(w_in),
+                       norm_weight, static_cast<bf16_t *>(w_in_folded), rows, dims->d_model);
+  else
+    hipLaunchKernelGGL(fold_cols_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(w_in),
+                       norm_weight, static_cast<float *>(w_in_folded), rows, dims->d_model);
+  return hipGetLastError() == hipSuccess ? ROM_OK : ROM_E_HIP;
+}
+
+int rom_block_forward(const rom_dims *dims, const rom_weights *w, const float *norm_weight, float eps,
+                      const void *x, int64_t B, int64_t L, const float *conv_state_in,
+                      const float *ssm_state_in, void *out, float *conv_state_out, float *ssm_state_out,
+                      void *ws, size_t ws_bytes, void *hip_stream) {
+  const BlockOpts blk = {norm_weight, eps};
+  return forward_impl(dims, w, x, B, L, conv_state_in, ssm_state_in, out, conv_state_out, ssm_state_out,
+                      ws, ws_bytes, static_cast<hipStream_t>(hip_stream), &blk);
+}
+
+int rom_block_step(const rom_dims *dims, const rom_weights *w, const float *norm_weight, float eps,
+                   const void *x, int64_t B, float *conv_state, float *ssm_state, void *out, void *ws,
+                   size_t ws_bytes, void *hip_stream) {
+  if (B > 0 && (!conv_state || !ssm_state)) return ROM_E_INVAL;
+  const BlockOpts blk = {norm_weight, eps};
+  return forward_impl(dims, w, x, B, 1, conv_state, ssm_state, out, conv_state, ssm_state, ws, ws_bytes,
+                      static_cast<hipStream_t>(hip_stream), &blk);
+}
+
+int rom_stack_forward(const rom_dims *dims, const rom_block *blocks, int n_layers, float eps,
+                      const void *x, int64_t B, int64_t L, const float *conv_state_in,
+                      const float *ssm_state_in, void *out, float *conv_state_out, float *ssm_state_out,
+                      void *tmp, void *ws, size_t ws_bytes, void *hip_stream) {
+  int rc = check_dims(dims);
+  if (rc != ROM_OK) return rc;
+  if (!blocks || n_layers < 1 || B < 0 || L < 0) return ROM_E_INVAL;
+  if (n_layers > 1 && (!tmp || tmp == x || tmp == out || !aligned16(tmp))) return ROM_E_INVAL;
+  for (int j = 0; j < n_layers; ++j) {   // refuse the whole call before the first layer is launched
+    rc = check_weights(dims, &blocks[j].w);
+    if (rc != ROM_OK) return rc;
+    if (!blocks[j].norm_weight || !aligned16(blocks[j].norm_weight)) return ROM_E_INVAL;
+  }
+  if (B == 0 || L == 0) return ROM_OK;
+  const size_t conv_per = static_cast<size_t>(B) * dims->d_inner * 3, ssm_per = static_cast<size_t>(B) * dims->d_inner * 16;
+  const void *src = x;
+  for (int j = 0; j < n_layers; ++j) {
+    // the layers write out and tmp in turn, the last one out
+    void *dst = ((n_layers - 1 - j) & 1) ? tmp : out;
+    const BlockOpts blk = {blocks[j].norm_weight, eps};
+    rc = forward_impl(dims, &blocks[j].w, src, B, L, conv_state_in ? conv_state_in + j * conv_per : nullptr,
+                      ssm_state_in ? ssm_state_in + j * ssm_per : nullptr, dst,
+                      conv_state_out ? conv_state_out + j * conv_per : nullptr,
+                      ssm_state_out ? ssm_state_out + j * ssm_per : nullptr, ws, ws_bytes,
+                      static_cast<hipStream_t>(hip_stream), &blk);
+    if (rc != ROM_OK) return rc;
+    src = dst;
+  }
+  return ROM_OK;
+}
+
+int rom_stack_step(const rom_dims *dims, const rom_block *blocks, int n_layers, float eps, const void *x,
+                   int64_t B, float *conv_state, float *ssm_state, void *out, void *tmp, void *ws,
+                   size_t ws_bytes, void *hip_stream) {
+  if (B > 0 && (!conv_state || !ssm_state)) return ROM_E_INVAL;
+  return rom_stack_forward(dims, blocks, n_layers, eps, x, B, 1, conv_state, ssm_state, out, conv_state,
+                           ssm_state, tmp, ws, ws_bytes, hip_stream);
 }
 
 int rom_step(const rom_dims *dims, const rom_weights *w, const void *x, int64_t B, float *conv_state,

@@ -93,12 +93,15 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmArgs &a, int BM, int 
 }
 
 // epilogue variants of the MFMA kernel (compile-time, so the store loop has no branches)
-enum { kEpiPlain = 0, kEpiBiasSoftplus = 1, kEpiRowScale = 2, kEpiPlainF32 = 3 };
+enum { kEpiPlain = 0, kEpiBiasSoftplus = 1, kEpiRowScale = 2, kEpiPlainF32 = 3, kEpiRowScaleResidual = 4 };
 
 __device__ __forceinline__ void store_out(const GemmArgs &a, int64_t crow, int col, float v) {
   if (a.bias) v += a.bias[col];
   if (a.softplus) v = softplus_f32(v);
   if (a.row_scale) v *= a.row_scale[crow];
+  if (a.residual)
+    v += a.dtype == ROM_DTYPE_F32 ? static_cast<const float *>(a.residual)[crow * a.ldc + col]
+                                  : bf16_to_f32(static_cast<const bf16_t *>(a.residual)[crow * a.ldc + col]);
   if (a.c_is_f32 || a.dtype == ROM_DTYPE_F32)
     static_cast<float *>(a.C)[blockIdx.y * a.c_split_stride + crow * a.ldc + col] = v;
   else
@@ -155,7 +158,7 @@ __device__ __forceinline__ void mfma_epilogue(const GemmArgs &a, const TileCoord
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       float scale = 1.0f;
-      if (EPI == kEpiRowScale) {
+      if (EPI == kEpiRowScale || EPI == kEpiRowScaleResidual) {
         const int64_t p = tc.row0 + wm * WTM + i * 32 + frag_row;
         scale = p < tc.row_end ? a.row_scale[a.c_rows ? a.c_rows[p] : p] : 0.0f;
       }
@@ -174,7 +177,7 @@ __device__ __forceinline__ void mfma_epilogue(const GemmArgs &a, const TileCoord
             v[0] = softplus_fast(v[0] + b4.x); v[1] = softplus_fast(v[1] + b4.y);
             v[2] = softplus_fast(v[2] + b4.z); v[3] = softplus_fast(v[3] + b4.w);
           }
-          if (EPI == kEpiRowScale) {
+          if (EPI == kEpiRowScale || EPI == kEpiRowScaleResidual) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[r] *= scale;
           }
@@ -190,7 +193,20 @@ __device__ __forceinline__ void mfma_epilogue(const GemmArgs &a, const TileCoord
         const int64_t p = tc.row0 + wm * WTM + i * 32 + row;
         if (row < 32 && p < tc.row_end && col < a.N) {
           const int64_t crow = a.c_rows ? a.c_rows[p] : p;
-          const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * kPitch + chunk * 16);
+          uint4 v = *reinterpret_cast<const uint4 *>(stage + row * kPitch + chunk * 16);
+          if (EPI == kEpiRowScaleResidual) {
+            // skip connection: the block's input row, in the output's layout, is added to the
+            // (already rounded) branch output here, where a lane holds 8 consecutive columns
+            const u32x4_t res = *reinterpret_cast<const u32x4_t *>(
+                static_cast<const bf16_t *>(a.residual) + crow * a.ldc + col);
+            unsigned int *vw = &v.x;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+              const float lo = __uint_as_float(vw[w] << 16) + __uint_as_float(res[w] << 16);
+              const float hi = __uint_as_float(vw[w] & 0xFFFF0000u) + __uint_as_float(res[w] & 0xFFFF0000u);
+              vw[w] = pack_bf16x2(lo, hi);
+            }
+          }
           *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.C) + crow * a.ldc + col) = v;
         }
       }
@@ -834,7 +850,7 @@ hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
 hipError_t launch_grouped_gemm(const GemmArgs &args, hipStream_t s) {
   if (args.M <= 0) return hipSuccess;
   GemmArgs a = args;
-  if (a.k_splits < 1 || !a.c_is_f32 || a.bias || a.row_scale) a.k_splits = 1;   // partial sums need a plain fp32 output
+  if (a.k_splits < 1 || !a.c_is_f32 || a.bias || a.row_scale || a.residual) a.k_splits = 1;   // partial sums need a plain fp32 output
   a.k_per_split = static_cast<int>(ceil_div(ceil_div(a.K, a.k_splits), 64) * 64);
   a.k_splits = static_cast<int>(ceil_div(a.K, a.k_per_split));
   const int out_align = a.c_is_f32 ? 4 : 8;      // elements per output store
@@ -844,7 +860,8 @@ hipError_t launch_grouped_gemm(const GemmArgs &args, hipStream_t s) {
                        (reinterpret_cast<uintptr_t>(a.C) % 16 == 0) && a.a_span < (1ll << 32) &&
                        static_cast<int64_t>(a.N) * a.K < (1ll << 32) &&
                        !(a.bias && !a.softplus) && !(a.softplus && !a.bias) &&
-                       !(a.row_scale && (a.bias || a.c_is_f32)) && !(a.bias && a.c_is_f32);
+                       !(a.row_scale && (a.bias || a.c_is_f32)) && !(a.bias && a.c_is_f32) &&
+                       !(a.residual && !a.row_scale) && (reinterpret_cast<uintptr_t>(a.residual) % 16 == 0);
   if (!mfma_ok) {
     const dim3 grid(grid_tiles(a, kSB, kSB), a.k_splits);
     if (a.dtype == ROM_DTYPE_BF16)
@@ -885,6 +902,7 @@ hipError_t launch_grouped_gemm(const GemmArgs &args, hipStream_t s) {
     }
     return launch_mfma_tiles<kEpiBiasSoftplus>(a, s);
   }
+  if (a.row_scale && a.residual) return launch_mfma_tiles<kEpiRowScaleResidual>(a, s);
   if (a.row_scale) return launch_mfma_tiles<kEpiRowScale>(a, s);
   // short inner dimension, many rows, wide output: the streaming kernel without its activation
   if (kUseSmallK && a.lda >= a.K && a.M < (1ll << 31) && a.M >= 4096 && a.N >= 1024) {

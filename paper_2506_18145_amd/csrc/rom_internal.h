@@ -40,10 +40,12 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // ---------------------------------------------------------------- routing (Eq. (9))
 // logits may be NULL.  tok_of_pos[p] = perm[p] / K.  block_counts: i32 [route_blocks(S), E].
+// norm_w (f32 [d_model]) != NULL: route on the RMS-normalised input and write rstd (f32 [N]).
 int64_t route_blocks(int64_t n_slots);
 hipError_t launch_route_topk(int dtype, const void *x, const void *w_router, const float *b_router,
                              int64_t n_tokens, int d_model, int n_experts, int top_k, int gate_mode,
-                             int32_t *expert_idx, float *gate, float *logits, hipStream_t s);
+                             int32_t *expert_idx, float *gate, float *logits, const float *norm_w,
+                             float norm_eps, float *rstd, hipStream_t s);
 hipError_t launch_permutation(const int32_t *expert_idx, int64_t n_slots, int n_experts, int top_k,
                               int32_t *block_counts, int32_t *counts, int32_t *offsets,
                               int32_t *perm, int32_t *inv_perm, int32_t *tok_of_pos, hipStream_t s);
@@ -76,6 +78,7 @@ struct GemmArgs {
   const float *bias;         // [N] or NULL: added before softplus
   int softplus;              // apply softplus after bias
   const float *row_scale;    // indexed by c_row (NULL = 1): multiplies the row
+  const void *residual;      // type T, laid out like C (row c_row, pitch ldc), or NULL: added after the row scale
   int k_splits;              // > 1: slice the inner dimension; slice s writes its partial sums (fp32, plain
                              // epilogue only) to C + s * c_split_stride; the consumer adds the slices up
   int64_t c_split_stride;    // elements between the outputs of consecutive slices
@@ -84,10 +87,12 @@ struct GemmArgs {
 hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s);
 
 // ---------------------------------------------------------------- sequence kernels
-// sum over the K slots of a token: dst[n, :] = sum_k src[inv_perm[n*K+k], :]
+// sum over the K slots of a token: dst[n, :] = act(row_scale[n] * sum_k src[inv_perm[n*K+k], :] + bias)
+// (row_scale f32 [n_tokens] or NULL, bias f32 [n_cols] or NULL)
 hipError_t launch_slot_sum(int src_is_f32, int dst_is_f32, const void *src, int64_t ld_src, void *dst,
                            int64_t ld_dst, const int32_t *inv_perm, int64_t n_tokens, int top_k,
-                           int n_cols, const float *bias, int softplus, hipStream_t s);
+                           int n_cols, const float *bias, int softplus, const float *row_scale,
+                           hipStream_t s);
 // xdbl (f32 [*, R + 32], token order or sorted) -> dt_low (T [N, R]) and bc (f32 [N, 32])
 hipError_t launch_split_xdbl(int dtype, const float *xdbl, int n_slices, int64_t slice_stride,
                              const int32_t *inv_perm, int top_k, int64_t n_tokens, int dt_rank,
@@ -103,8 +108,9 @@ hipError_t launch_scan_gate(int dtype, const void *u, const void *dt, const floa
                             int64_t ld_z, const float *A_log, const float *D, const float *h_in,
                             float *h_out, void *g, int64_t B, int64_t L, int d_inner, float *chunk_q,
                             float *chunk_p, hipStream_t s);
-// out[n, :] = sum_k gate[n*K+k] * op[inv_perm[n*K+k], :]
+// out[n, :] = (residual[n, :] if given) + sum_k gate[n*K+k] * op[inv_perm[n*K+k], :]
 hipError_t launch_combine(int dtype, const void *op, const int32_t *inv_perm, const float *gate,
-                          void *out, int64_t n_tokens, int top_k, int d_model, hipStream_t s);
+                          void *out, int64_t n_tokens, int top_k, int d_model, const void *residual,
+                          hipStream_t s);
 
 }  // namespace rom

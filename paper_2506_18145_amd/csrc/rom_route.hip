@@ -59,13 +59,18 @@ template <> struct Vec8<float> {
 // Lane e then owns logit e of each token and the wave does K arg-max rounds by ballot.
 // WPT = 4 is for launches with few tokens (the recurrent step): one token per wave would leave
 // most of the chip idle behind a long chain of dependent loads.
-template <typename T, int EMAX, int TOK, int WPT>
+// NORM: the router sees the RMS-normalised input x * rstd * norm_w of a pre-norm block.  The
+// per-token sum of squares rides along with the dot products (x is read once either way),
+// rstd = 1 / sqrt(mean(x^2) + eps) multiplies the finished sums and is written out for the in
+// projection's epilogue.
+template <typename T, int EMAX, int TOK, int WPT, bool NORM>
 __global__ __launch_bounds__(256) void route_topk_kernel(
     const T *__restrict__ x, const T *__restrict__ w_router, const float *__restrict__ b_router,
     int64_t n_tokens, int d_model, int n_experts, int top_k, int gate_mode,
-    int32_t *__restrict__ expert_idx, float *__restrict__ gate, float *__restrict__ logits) {
+    int32_t *__restrict__ expert_idx, float *__restrict__ gate, float *__restrict__ logits,
+    const float *__restrict__ norm_w, float norm_eps, float *__restrict__ rstd_out) {
   static_assert(WPT == 1 || WPT == 4, "one wave or one block per token group");
-  __shared__ float part[WPT == 4 ? 4 * TOK * EMAX : 1];
+  __shared__ float part[WPT == 4 ? 4 * TOK * (EMAX + 1) : 1];   // [wave][token][EMAX sums | sum of squares]
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t group_id = WPT == 4 ? static_cast<int64_t>(blockIdx.x)
                                     : (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / kWave;
@@ -77,6 +82,9 @@ __global__ __launch_bounds__(256) void route_topk_kernel(
   for (int t = 0; t < TOK; ++t)
 #pragma unroll
     for (int e = 0; e < EMAX; ++e) acc[t][e] = 0.0f;
+  float ss[TOK];
+#pragma unroll
+  for (int t = 0; t < TOK; ++t) ss[t] = 0.0f;
 
   const int first = (WPT == 4 ? wave * kWave + lane : lane) * 8;
   for (int d0 = first; d0 < d_model; d0 += WPT * kWave * 8) {
@@ -85,6 +93,24 @@ __global__ __launch_bounds__(256) void route_topk_kernel(
     for (int t = 0; t < TOK; ++t) {
       const int64_t tok = (tok0 + t < n_tokens) ? tok0 + t : n_tokens - 1;
       xv[t].load(x + tok * d_model + d0);
+    }
+    float xs[TOK][8];
+    if (NORM) {
+      Vec8<float> nw;
+      nw.load(norm_w + d0);
+#pragma unroll
+      for (int t = 0; t < TOK; ++t)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float xf = xv[t].get(i);
+          ss[t] = fmaf(xf, xf, ss[t]);
+          xs[t][i] = xf * nw.get(i);
+        }
+    } else {
+#pragma unroll
+      for (int t = 0; t < TOK; ++t)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) xs[t][i] = xv[t].get(i);
     }
 #pragma unroll
     for (int e = 0; e < EMAX; ++e) {
@@ -95,7 +121,7 @@ __global__ __launch_bounds__(256) void route_topk_kernel(
         for (int i = 0; i < 8; ++i) {
           const float wf = wv.get(i);
 #pragma unroll
-          for (int t = 0; t < TOK; ++t) acc[t][e] = fmaf(xv[t].get(i), wf, acc[t][e]);
+          for (int t = 0; t < TOK; ++t) acc[t][e] = fmaf(xs[t][i], wf, acc[t][e]);
         }
       }
     }
@@ -103,12 +129,17 @@ __global__ __launch_bounds__(256) void route_topk_kernel(
 
   if (WPT == 4) {
 #pragma unroll
-    for (int t = 0; t < TOK; ++t)
+    for (int t = 0; t < TOK; ++t) {
 #pragma unroll
       for (int e = 0; e < EMAX; ++e) {
         const float s = wave_sum(acc[t][e]);
-        if (lane == 0) part[(wave * TOK + t) * EMAX + e] = s;
+        if (lane == 0) part[(wave * TOK + t) * (EMAX + 1) + e] = s;
       }
+      if (NORM) {
+        const float s = wave_sum(ss[t]);
+        if (lane == 0) part[(wave * TOK + t) * (EMAX + 1) + EMAX] = s;
+      }
+    }
     __syncthreads();
     if (wave != 0) return;
   }
@@ -116,20 +147,33 @@ __global__ __launch_bounds__(256) void route_topk_kernel(
 #pragma unroll
   for (int t = 0; t < TOK; ++t) {
     const int64_t tok = tok0 + t;
+    float rstd = 1.0f;
+    if (NORM) {
+      float sq;
+      if (WPT == 4) {
+        sq = part[t * (EMAX + 1) + EMAX];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) sq += part[(w * TOK + t) * (EMAX + 1) + EMAX];
+      } else {
+        sq = wave_sum(ss[t]);
+      }
+      rstd = 1.0f / sqrtf(sq / static_cast<float>(d_model) + norm_eps);
+      if (lane == 0 && tok < n_tokens) rstd_out[tok] = rstd;
+    }
     // lane e keeps logit e
     float mine = -INFINITY;
     if (WPT == 4) {
       if (lane < n_experts && lane < EMAX) {
-        float s = part[t * EMAX + lane];
+        float s = part[t * (EMAX + 1) + lane];
 #pragma unroll
-        for (int w = 1; w < 4; ++w) s += part[(w * TOK + t) * EMAX + lane];
-        mine = s + (b_router ? b_router[lane] : 0.0f);
+        for (int w = 1; w < 4; ++w) s += part[(w * TOK + t) * (EMAX + 1) + lane];
+        mine = s * rstd + (b_router ? b_router[lane] : 0.0f);
       }
     } else {
 #pragma unroll
       for (int e = 0; e < EMAX; ++e) {
         const float s = wave_sum(acc[t][e]);
-        if (lane == e && e < n_experts) mine = s + (b_router ? b_router[e] : 0.0f);
+        if (lane == e && e < n_experts) mine = s * rstd + (b_router ? b_router[e] : 0.0f);
       }
     }
     if (tok >= n_tokens) continue;
@@ -370,19 +414,21 @@ __global__ __launch_bounds__(kWave) void balance_finish_kernel(
   if (e == 0) *loss = alpha * static_cast<float>(n_experts) * total;
 }
 
-template <typename T>
+template <typename T, bool NORM>
 hipError_t route_dispatch(const void *x, const void *w_router, const float *b_router,
                           int64_t n_tokens, int d_model, int n_experts, int top_k, int gate_mode,
-                          int32_t *expert_idx, float *gate, float *logits, hipStream_t s) {
+                          int32_t *expert_idx, float *gate, float *logits, const float *norm_w,
+                          float norm_eps, float *rstd, hipStream_t s) {
   const T *xp = static_cast<const T *>(x);
   const T *wp = static_cast<const T *>(w_router);
 #define ROM_ROUTE_LAUNCH(EMAX, TOK, WPT)                                                         \
   do {                                                                                           \
     const int64_t groups = ceil_div(n_tokens, TOK);                                              \
     const int64_t blocks = WPT == 4 ? groups : ceil_div(groups, 4);                              \
-    hipLaunchKernelGGL((route_topk_kernel<T, EMAX, TOK, WPT>), dim3(static_cast<unsigned>(blocks)), \
-                       dim3(256), 0, s, xp, wp, b_router, n_tokens, d_model, n_experts, top_k,   \
-                       gate_mode, expert_idx, gate, logits);                                     \
+    hipLaunchKernelGGL((route_topk_kernel<T, EMAX, TOK, WPT, NORM>),                             \
+                       dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, xp, wp, b_router,   \
+                       n_tokens, d_model, n_experts, top_k, gate_mode, expert_idx, gate, logits, \
+                       norm_w, norm_eps, rstd);                                                  \
   } while (0)
   // few tokens: one token per block / per wavefront so that the launch still spreads over the chip
   if (n_tokens <= 1024 && n_experts <= 8) ROM_ROUTE_LAUNCH(8, 1, 4);
@@ -403,12 +449,16 @@ int64_t route_blocks(int64_t n_slots) { return ceil_div(n_slots, kSortBlock); }
 
 hipError_t launch_route_topk(int dtype, const void *x, const void *w_router, const float *b_router,
                              int64_t n_tokens, int d_model, int n_experts, int top_k, int gate_mode,
-                             int32_t *expert_idx, float *gate, float *logits, hipStream_t s) {
-  if (dtype == ROM_DTYPE_BF16)
-    return route_dispatch<bf16_t>(x, w_router, b_router, n_tokens, d_model, n_experts, top_k,
-                                  gate_mode, expert_idx, gate, logits, s);
-  return route_dispatch<float>(x, w_router, b_router, n_tokens, d_model, n_experts, top_k, gate_mode,
-                               expert_idx, gate, logits, s);
+                             int32_t *expert_idx, float *gate, float *logits, const float *norm_w,
+                             float norm_eps, float *rstd, hipStream_t s) {
+#define ROM_ROUTE_ARGS x, w_router, b_router, n_tokens, d_model, n_experts, top_k, gate_mode, expert_idx, gate, \
+                       logits, norm_w, norm_eps, rstd, s
+  if (norm_w)
+    return dtype == ROM_DTYPE_BF16 ? route_dispatch<bf16_t, true>(ROM_ROUTE_ARGS)
+                                   : route_dispatch<float, true>(ROM_ROUTE_ARGS);
+  return dtype == ROM_DTYPE_BF16 ? route_dispatch<bf16_t, false>(ROM_ROUTE_ARGS)
+                                 : route_dispatch<float, false>(ROM_ROUTE_ARGS);
+#undef ROM_ROUTE_ARGS
 }
 
 size_t balance_scratch_bytes(int n_experts) {

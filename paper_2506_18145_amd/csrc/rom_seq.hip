@@ -64,7 +64,8 @@ __global__ __launch_bounds__(256) void slot_sum_kernel(const TS *__restrict__ sr
                                                        TD *__restrict__ dst, int64_t ld_dst,
                                                        const int32_t *__restrict__ inv_perm,
                                                        int64_t n_tokens, int top_k, int n_cols,
-                                                       const float *__restrict__ bias, int softplus) {
+                                                       const float *__restrict__ bias, int softplus,
+                                                       const float *__restrict__ row_scale) {
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
   const int pairs = n_cols / 2;
   if (idx >= n_tokens * pairs) return;
@@ -76,6 +77,7 @@ __global__ __launch_bounds__(256) void slot_sum_kernel(const TS *__restrict__ sr
     a0 += to_f32(src[row * ld_src + c]);
     a1 += to_f32(src[row * ld_src + c + 1]);
   }
+  if (row_scale) { a0 *= row_scale[n]; a1 *= row_scale[n]; }
   if (bias) { a0 += bias[c]; a1 += bias[c + 1]; }
   if (softplus) { a0 = softplus_f32(a0); a1 = softplus_f32(a1); }
   dst[n * ld_dst + c] = from_f32<TD>(a0);
@@ -570,7 +572,8 @@ __global__ __launch_bounds__(256) void slot_sum8_kernel(const TS *__restrict__ s
                                                         TD *__restrict__ dst, int64_t ld_dst,
                                                         const int32_t *__restrict__ inv_perm,
                                                         int64_t n_tokens, int top_k, int n_cols,
-                                                        const float *__restrict__ bias, int softplus) {
+                                                        const float *__restrict__ bias, int softplus,
+                                                        const float *__restrict__ row_scale) {
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
   const int groups = n_cols / 8;
   if (idx >= n_tokens * groups) return;
@@ -587,6 +590,11 @@ __global__ __launch_bounds__(256) void slot_sum8_kernel(const TS *__restrict__ s
     v.to_floats(f);
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] += f[i];
+  }
+  if (row_scale) {
+    const float rs = row_scale[n];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] *= rs;
   }
   if (bias) {
     const float4 b0 = ld_f4(bias + c), b1 = ld_f4(bias + c + 4);
@@ -610,7 +618,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const T *__restrict__ op,
                                                       const int32_t *__restrict__ inv_perm,
                                                       const float *__restrict__ gate,
                                                       T *__restrict__ out, int64_t n_tokens,
-                                                      int top_k, int d_model) {
+                                                      int top_k, int d_model,
+                                                      const T *__restrict__ residual) {
   constexpr int V = Chunk<T>::kElems;
   const int groups = d_model / V;
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -620,6 +629,12 @@ __global__ __launch_bounds__(256) void combine_kernel(const T *__restrict__ op,
   float acc[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+  if (residual) {                 // skip connection: start from the block's input row
+    Chunk<T> r;
+    r.load(residual + n * d_model + c0);
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = r.get(i);
+  }
   for (int k = 0; k < top_k; ++k) {
     const int64_t row = inv_perm[n * top_k + k];
     const float gk = gate[n * top_k + k];
@@ -640,7 +655,8 @@ inline dim3 grid1d(int64_t work, int block) { return dim3(static_cast<unsigned>(
 
 hipError_t launch_slot_sum(int src_is_f32, int dst_is_f32, const void *src, int64_t ld_src, void *dst,
                            int64_t ld_dst, const int32_t *inv_perm, int64_t n_tokens, int top_k,
-                           int n_cols, const float *bias, int softplus, hipStream_t s) {
+                           int n_cols, const float *bias, int softplus, const float *row_scale,
+                           hipStream_t s) {
   const bool wide = n_cols % 8 == 0 && ld_src % 8 == 0 && ld_dst % 8 == 0 &&
                     reinterpret_cast<uintptr_t>(src) % 16 == 0 && reinterpret_cast<uintptr_t>(dst) % 16 == 0 &&
                     (!bias || reinterpret_cast<uintptr_t>(bias) % 16 == 0);
@@ -650,11 +666,11 @@ hipError_t launch_slot_sum(int src_is_f32, int dst_is_f32, const void *src, int6
     if (wide)                                                                                     \
       hipLaunchKernelGGL((slot_sum8_kernel<TS, TD>), grid, dim3(256), 0, s, static_cast<const TS *>(src), \
                          ld_src, static_cast<TD *>(dst), ld_dst, inv_perm, n_tokens, top_k, n_cols, \
-                         bias, softplus);                                                         \
+                         bias, softplus, row_scale);                                              \
     else                                                                                          \
       hipLaunchKernelGGL((slot_sum_kernel<TS, TD>), grid, dim3(256), 0, s, static_cast<const TS *>(src), \
                          ld_src, static_cast<TD *>(dst), ld_dst, inv_perm, n_tokens, top_k, n_cols, \
-                         bias, softplus);                                                         \
+                         bias, softplus, row_scale);                                              \
   } while (0)
   if (src_is_f32 && dst_is_f32) ROM_SS(float, float);
   else if (src_is_f32) ROM_SS(float, bf16_t);
@@ -779,15 +795,18 @@ hipError_t launch_scan_gate(int dtype, const void *u, const void *dt, const floa
 }
 
 hipError_t launch_combine(int dtype, const void *op, const int32_t *inv_perm, const float *gate,
-                          void *out, int64_t n_tokens, int top_k, int d_model, hipStream_t s) {
+                          void *out, int64_t n_tokens, int top_k, int d_model, const void *residual,
+                          hipStream_t s) {
   const int V = dtype == ROM_DTYPE_BF16 ? 8 : 4;
   const dim3 grid = grid1d(n_tokens * (d_model / V), 256);
   if (dtype == ROM_DTYPE_BF16)
     hipLaunchKernelGGL(combine_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(op),
-                       inv_perm, gate, static_cast<bf16_t *>(out), n_tokens, top_k, d_model);
+                       inv_perm, gate, static_cast<bf16_t *>(out), n_tokens, top_k, d_model,
+                       static_cast<const bf16_t *>(residual));
   else
     hipLaunchKernelGGL(combine_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(op),
-                       inv_perm, gate, static_cast<float *>(out), n_tokens, top_k, d_model);
+                       inv_perm, gate, static_cast<float *>(out), n_tokens, top_k, d_model,
+                       static_cast<const float *>(residual));
   return hipGetLastError();
 }
 

@@ -10,6 +10,7 @@ from .configs import (  # noqa: F401
     CONFIGS,
     get_config,
     make_weights,
+    make_stack_weights,
     make_input,
     make_states,
     make_step_inputs,

@@ -17,6 +17,7 @@ layer's weight):
     w_dt     [E_x, d_inner, dt_rank]
     dt_bias  [d_inner] (fp32)   A_log [d_inner, d_state] (fp32)   D [d_inner] (fp32)
     w_out    [E, d_model, d_inner]
+    norm_w   [d_model] (fp32)      scale of the pre-norm of the residual block
 
 All arrays are returned as float32.  For bf16 workloads the tensors that the
 layer stores in bf16 (x, w_router, w_in, w_x, w_dt, w_out) hold values that
@@ -118,7 +119,7 @@ def _store(cfg: RomConfig, a: np.ndarray) -> np.ndarray:
 
 
 # tensor ids (seed = 1000 * cfg_id + id)
-_T_X, _T_WR, _T_WIN, _T_CW, _T_CB, _T_WX, _T_WDT, _T_DTB, _T_WOUT, _T_CS, _T_SS, _T_XS = range(1, 13)
+_T_X, _T_WR, _T_WIN, _T_CW, _T_CB, _T_WX, _T_WDT, _T_DTB, _T_WOUT, _T_CS, _T_SS, _T_XS, _T_NORM = range(1, 14)
 
 
 def make_weights(cfg: RomConfig) -> Dict[str, Optional[np.ndarray]]:
@@ -143,7 +144,16 @@ def make_weights(cfg: RomConfig) -> Dict[str, Optional[np.ndarray]]:
     w["A_log"] = np.log(np.tile(np.arange(1, Ds + 1, dtype=np.float64), (De, 1))).astype(np.float32)
     w["D"] = np.ones((De,), dtype=np.float32)
     w["w_out"] = _store(cfg, _normal(cfg, _T_WOUT, (E, Dm, De), s))
+    # scale of the block's pre-norm (fp32): 1 at initialisation in any trained model; spread to
+    # [0.7, 1.3] here so that a missing or misplaced scale cannot hide
+    w["norm_w"] = _rng(cfg, _T_NORM).uniform(0.7, 1.3, (Dm,)).astype(np.float32)
     return w
+
+
+def make_stack_weights(cfg: RomConfig, n_layers: int):
+    """Per-layer weight dicts of a stack of blocks: layer j draws from the seeds of
+    cfg_id + 1000 * (j + 1), so no two layers (and no other workload) share a tensor."""
+    return [make_weights(replace(cfg, cfg_id=cfg.cfg_id + 1000 * (j + 1))) for j in range(n_layers)]
 
 
 def make_input(cfg: RomConfig) -> np.ndarray:

@@ -30,10 +30,15 @@ def f64_weights(w):
     return {k: (None if v is None else np.asarray(v, np.float64)) for k, v in w.items()}
 
 
-def check_routing(cfg, gpu, x_np, w_np):
-    """gpu: dict of numpy arrays from the HIP path.  Returns (expert_idx to hand the oracle, n_excluded)."""
+BLOCK_EPS = 1e-5
+
+
+def check_routing(cfg, gpu, x_np, w_np, block=False):
+    """gpu: dict of numpy arrays from the HIP path.  Returns (expert_idx to hand the oracle, n_excluded).
+    block: the router sees the RMS-normalised input."""
     n_tok = gpu["expert_idx"].shape[0]
-    logits = O.router_logits(x_np.reshape(n_tok, -1), w_np["w_router"], w_np.get("b_router"))
+    x_r = O.rms_norm(x_np, w_np["norm_w"], BLOCK_EPS) if block else x_np
+    logits = O.router_logits(x_r.reshape(n_tok, -1), w_np["w_router"], w_np.get("b_router"))
     own = O.topk_select(logits, cfg.top_k)
     close = O.topk_margin(logits, cfg.top_k) < MARGIN
     idx = gpu["expert_idx"].astype(np.int32)
@@ -57,14 +62,18 @@ def check_routing(cfg, gpu, x_np, w_np):
     return idx, int(close.sum())
 
 
-def run_layer(cfg, conv_state=None, ssm_state=None, x_np=None, w_np=None, return_states=True):
+def run_layer(cfg, conv_state=None, ssm_state=None, x_np=None, w_np=None, return_states=True, block=False):
+    """block: the pre-norm residual block (rom_block_forward) instead of the bare layer."""
     w_np = make_weights(cfg) if w_np is None else w_np
     x_np = make_input(cfg) if x_np is None else x_np
     layer = RomLayer(cfg, w_np)
     x = layer.to_device(x_np)
     cs = None if conv_state is None else layer.to_device(conv_state, typed=False)
     ss = None if ssm_state is None else layer.to_device(ssm_state, typed=False)
-    out, conv_out, ssm_out = layer.forward(x, cs, ss, return_states=True)
+    if block:
+        out, conv_out, ssm_out = layer.block_forward(x, cs, ss, return_states=True, eps=BLOCK_EPS)
+    else:
+        out, conv_out, ssm_out = layer.forward(x, cs, ss, return_states=True)
     torch.cuda.synchronize()
     B, L = x.shape[0], x.shape[1]
     gpu = {name: to_np(layer.ws_view(name, B, L)) for name in
@@ -74,9 +83,13 @@ def run_layer(cfg, conv_state=None, ssm_state=None, x_np=None, w_np=None, return
     return layer, gpu, x_np, w_np
 
 
-def compare_layer(cfg, gpu, x_np, w_np, conv_state=None, ssm_state=None, stages=True):
-    idx, n_excl = check_routing(cfg, gpu, x_np, w_np)
-    ref = O.rom_layer_forward(x_np, w_np, cfg.top_k, cfg.gate_mode, conv_state, ssm_state, expert_idx=idx)
+def compare_layer(cfg, gpu, x_np, w_np, conv_state=None, ssm_state=None, stages=True, block=False):
+    idx, n_excl = check_routing(cfg, gpu, x_np, w_np, block)
+    if block:
+        ref = O.rom_block_forward(x_np, w_np, cfg.top_k, cfg.gate_mode, BLOCK_EPS, conv_state, ssm_state,
+                                  expert_idx=idx)
+    else:
+        ref = O.rom_layer_forward(x_np, w_np, cfg.top_k, cfg.gate_mode, conv_state, ssm_state, expert_idx=idx)
     tol = TOL[cfg.dtype]
     errs = {}
     if stages:
@@ -88,6 +101,14 @@ def compare_layer(cfg, gpu, x_np, w_np, conv_state=None, ssm_state=None, stages=
         errs["dt"] = rel_err(gpu["dt"], ref["dt"])
         errs["g"] = rel_err(gpu["g"], ref["g"])
     errs["out"] = rel_err(gpu["out"], ref["out"])
+    if block:
+        # the branch alone, so that an error in it cannot hide behind a large skip term; the
+        # output's own rounding (unit roundoff of the activation type: 8 significant bits in
+        # bf16, 24 in fp32, times |out|) is allowed on top
+        got_branch = gpu["out"].astype(np.float64) - np.asarray(x_np, np.float64)
+        ulp = 2.0 ** -8 if cfg.dtype == "bf16" else 2.0 ** -24
+        slack = ulp * np.max(np.abs(ref["out"])) / np.max(np.abs(ref["branch"]))
+        errs["branch"] = max(rel_err(got_branch, ref["branch"]) - slack, 0.0)
     errs["ssm_state"] = rel_err(gpu["ssm_state"], ref["ssm_state"])
     errs["conv_state"] = rel_err(gpu["conv_state"], ref["conv_state"])
     print(f"[{cfg.name}] excluded={n_excl} counts={gpu['counts'].tolist()} "

@@ -39,6 +39,7 @@ def test_struct_sizes_match_header():
     assert ctypes.sizeof(binding.RomDims) == 40
     assert ctypes.sizeof(binding._RomWeights) == 11 * ctypes.sizeof(ctypes.c_void_p)
     assert ctypes.sizeof(binding._RomWsLayout) == 14 * ctypes.sizeof(ctypes.c_size_t)
+    assert ctypes.sizeof(binding._RomBlock) == 12 * ctypes.sizeof(ctypes.c_void_p)
 
 
 def test_workspace_bytes_and_layout(lib):
@@ -166,3 +167,45 @@ def test_balance_stats_arguments_and_scratch_placement(lib):
     for lay in lays:
         assert lay["logits"] == lays[0]["logits"] and lay["xz"] == lays[0]["xz"]
         assert lay["xz"] - lay["logits"] >= N * E * 4 + 256 * E * 4
+
+
+def test_block_and_stack_arguments_are_checked_before_any_launch(lib):
+    from paper_2506_18145_amd import binding
+    d = _dims()
+    buf = ctypes.create_string_buffer(8192 + 256)
+    addr = (ctypes.addressof(buf) + 255) // 256 * 256
+    w = binding._RomWeights(*([addr] * 11))
+    F = ctypes.c_float
+    # no norm weight / negative eps / misaligned norm weight
+    assert lib.rom_block_forward(ctypes.byref(d), ctypes.byref(w), None, F(1e-5), addr, 1, 8, None, None,
+                                 addr + 4096, None, None, addr, 4096, None) == -1
+    assert lib.rom_block_forward(ctypes.byref(d), ctypes.byref(w), addr, F(-1.0), addr, 1, 8, None, None,
+                                 addr + 4096, None, None, addr, 4096, None) == -1
+    assert lib.rom_block_forward(ctypes.byref(d), ctypes.byref(w), addr + 4, F(1e-5), addr, 1, 8, None, None,
+                                 addr + 4096, None, None, addr, 4096, None) == -1
+    # a valid call shape with a workspace that is too small, and the empty call
+    assert lib.rom_block_forward(ctypes.byref(d), ctypes.byref(w), addr, F(1e-5), addr, 1, 8, None, None,
+                                 addr + 4096, None, None, addr, 4096, None) == -2
+    assert lib.rom_block_forward(ctypes.byref(d), ctypes.byref(w), addr, F(1e-5), addr, 0, 8, None, None,
+                                 addr + 4096, None, None, addr, 4096, None) == 0
+    assert lib.rom_block_step(ctypes.byref(d), ctypes.byref(w), addr, F(1e-5), addr, 4, None, None, addr + 4096,
+                              addr, 4096, None) == -1                   # a step needs its states
+    assert lib.rom_fold_norm(ctypes.byref(d), None, addr, addr, None) == -1
+    assert lib.rom_fold_norm(ctypes.byref(_dims(d_conv=3)), addr, addr, addr, None) == -3
+    blocks = (binding._RomBlock * 2)()
+    for b in blocks:
+        b.w = w
+        b.norm_weight = addr
+    call = lambda blk, n, tmp, out=addr + 4096, B=1: lib.rom_stack_forward(
+        ctypes.byref(d), blk, n, F(1e-5), addr, B, 8, None, None, out, None, None, tmp, addr, 4096, None)
+    assert call(blocks, 2, None) == -1                 # two layers need the scratch buffer
+    assert call(blocks, 2, addr) == -1                 # ... which must not alias x
+    assert call(blocks, 2, addr + 4096) == -1          # ... nor out
+    assert call(blocks, 0, addr + 2048) == -1
+    assert call(None, 2, addr + 2048) == -1
+    assert call(blocks, 2, addr + 2048) == -2          # all pointers fine, workspace too small
+    assert call(blocks, 2, addr + 2048, B=0) == 0
+    blocks[1].norm_weight = None                       # a bad second layer is refused before layer 0 runs
+    assert call(blocks, 2, addr + 2048) == -1
+    assert lib.rom_stack_step(ctypes.byref(d), blocks, 2, F(1e-5), addr, 4, None, None, addr + 4096,
+                              addr + 2048, addr, 4096, None) == -1

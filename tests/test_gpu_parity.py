@@ -7,10 +7,10 @@ import pytest
 import torch
 
 from oracle import rom_oracle as O
-from paper_2506_18145_amd import RomLayer
-from rom_synth import RomConfig, get_config, make_input, make_states, make_weights
+from paper_2506_18145_amd import RomLayer, RomStack
+from rom_synth import RomConfig, get_config, make_input, make_stack_weights, make_states, make_weights
 
-from gpu_util import MARGIN, TOL, check_routing, compare_layer, rel_err, run_layer, to_np
+from gpu_util import BLOCK_EPS, MARGIN, TOL, check_routing, compare_layer, rel_err, run_layer, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -317,3 +317,98 @@ def test_step_cfg4_decode_512_steps():
     every sequence through the first four."""
     cfg = get_config("cfg4")
     _step_run(cfg, 512, tracked=[3, 200], all_steps=4)
+
+
+# ---------------------------------------------------------------------------------------------
+# pre-norm residual block and stack of blocks
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("kw", [
+    dict(),
+    dict(dtype="fp32"),
+    dict(top_k=2, gate_mode=1),
+    dict(top_k=2, gate_mode=0, dtype="fp32"),
+    dict(routed_xdt=False),
+    dict(n_experts=1),
+    dict(batch=3, seq_len=1),
+    dict(batch=1, seq_len=1500, d_model=264, d_inner=528, dt_rank=24, cfg_id=58),
+])
+def test_block_small(kw):
+    """out = x + RoM(RMSNorm(x)) with the norm folded into the router and the in projection and
+    the skip fused into the last kernel, against the oracle's block; with incoming states too."""
+    cfg = small_cfg(weight_std=0.08, **kw)         # branch of the size of the skip term
+    x = make_input(cfg) * np.float32(1.7)          # off unit RMS, so that the 1/rms factor matters
+    from rom_synth import round_to_bf16
+    x = round_to_bf16(x) if cfg.dtype == "bf16" else x
+    _, gpu, x, w = run_layer(cfg, x_np=x, block=True)
+    compare_layer(cfg, gpu, x, w, block=True)
+    cs, ss = make_states(cfg)
+    _, gpu, x, w = run_layer(cfg, cs, ss, x_np=x, block=True)
+    compare_layer(cfg, gpu, x, w, cs, ss, block=True)
+
+
+@pytest.mark.parametrize("name,over", [("cfg1", {}), ("cfg3", dict(batch=1, seq_len=4096))])
+def test_block_big_tile_kernels(name, over):
+    """The block at sizes that take the 256-row tiles (row-scaled in projection, out projection
+    with the fused skip; the K = 2 case scales in the slot sum and adds the skip in the combine)."""
+    cfg = get_config(name, **over)
+    _, gpu, x, w = run_layer(cfg, block=True)
+    compare_layer(cfg, gpu, x, w, block=True)
+
+
+def test_block_step_matches_oracle_and_block_forward():
+    cfg = small_cfg(batch=5, seq_len=12, top_k=2, gate_mode=1, n_experts=8, cfg_id=59, weight_std=0.08)
+    w = make_weights(cfg)
+    x = make_input(cfg)
+    layer = RomLayer(cfg, w)
+    cs0, ss0 = make_states(cfg)
+    cs, ss = layer.to_device(cs0, typed=False), layer.to_device(ss0, typed=False)
+    xd = layer.to_device(x)
+    outs = []
+    for t in range(cfg.seq_len):
+        outs.append(to_np(layer.block_step(xd[:, t].contiguous(), cs, ss, eps=BLOCK_EPS)))
+    torch.cuda.synchronize()
+    got = np.stack(outs, axis=1)
+    # the steps' routing decisions, re-derived from the oracle per token (none inside the margin)
+    ref = O.rom_block_forward(x, w, cfg.top_k, cfg.gate_mode, BLOCK_EPS, cs0, ss0)
+    assert np.min(O.topk_margin(ref["logits"], cfg.top_k)) > 1e-4
+    tol = TOL[cfg.dtype]
+    assert rel_err(got, ref["out"]) <= tol
+    assert rel_err(to_np(ss), ref["ssm_state"]) <= tol
+    assert rel_err(to_np(cs), ref["conv_state"]) <= tol
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_stack_forward_and_step(dtype):
+    """rom_stack_forward is bit-identical to its blocks called one by one (same kernels in the same
+    order), carries a [n_layers, B, ...] state per layer, and - in fp32, where no token of any
+    layer sits near a routing boundary - matches the oracle's stack end to end."""
+    n_layers = 3
+    cfg = small_cfg(batch=2, seq_len=150, dtype=dtype, n_experts=4, top_k=1, cfg_id=63, weight_std=0.08)
+    ws = make_stack_weights(cfg, n_layers)
+    x = make_input(cfg)
+    layers = [RomLayer(cfg, w) for w in ws]
+    stack = RomStack(layers, eps=BLOCK_EPS, fold_in_place=False)
+    xd = layers[0].to_device(x)
+    out, conv_s, ssm_s = stack.forward(xd, return_states=True)
+    h = xd
+    for j, ly in enumerate(layers):
+        h, c_j, s_j = ly.block_forward(h, return_states=True, eps=BLOCK_EPS)
+        assert torch.equal(c_j, conv_s[j]) and torch.equal(s_j, ssm_s[j])
+    torch.cuda.synchronize()
+    assert torch.equal(h, out)
+    if dtype == "fp32":
+        ref_out, ref = O.rom_stack_forward(x, ws, cfg.top_k, cfg.gate_mode, BLOCK_EPS)
+        assert min(np.min(O.topk_margin(r["logits"], cfg.top_k)) for r in ref) > 1e-4
+        assert rel_err(to_np(out), ref_out) <= TOL["fp32"]
+        for j in range(n_layers):
+            assert rel_err(to_np(ssm_s[j]), ref[j]["ssm_state"]) <= TOL["fp32"]
+            assert rel_err(to_np(conv_s[j]), ref[j]["conv_state"]) <= TOL["fp32"]
+    # one more token through the stack from those states == the blocks' steps one by one
+    x1 = layers[0].to_device(make_input(small_cfg(batch=2, seq_len=1, dtype=dtype, cfg_id=61)))[:, 0].contiguous()
+    conv_a, ssm_a = conv_s.clone(), ssm_s.clone()
+    o_stack = stack.step(x1, conv_a, ssm_a)
+    h = x1
+    for j, ly in enumerate(layers):
+        h = ly.block_step(h, conv_s[j], ssm_s[j], eps=BLOCK_EPS)
+    torch.cuda.synchronize()
+    assert torch.equal(h, o_stack) and torch.equal(conv_a, conv_s) and torch.equal(ssm_a, ssm_s)
