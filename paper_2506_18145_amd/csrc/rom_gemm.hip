@@ -155,6 +155,26 @@ __device__ __forceinline__ void mfma_epilogue(const GemmArgs &a, const TileCoord
     constexpr int kRowsPerPass = 64 / kChunks;
     const int chunk = lane % kChunks, sub = lane / kChunks;
     const int col = tc.n0 + wn * WTN + chunk * 8;
+    constexpr int kPasses = (32 + kRowsPerPass - 1) / kRowsPerPass;
+    // skip connection: the block's input rows, in the output's layout.  All of them are fetched
+    // before the first output store: loads and stores retire through one in-order counter, so a
+    // load issued behind a store could only be waited for together with that store.
+    u32x4_t res[EPI == kEpiRowScaleResidual ? TM : 1][EPI == kEpiRowScaleResidual ? kPasses : 1];
+    if constexpr (EPI == kEpiRowScaleResidual) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int ps = 0; ps < kPasses; ++ps) {
+          const int row = ps * kRowsPerPass + sub;
+          const int64_t p = tc.row0 + wm * WTM + i * 32 + row;
+          res[i][ps] = u32x4_t{0u, 0u, 0u, 0u};
+          if (row < 32 && p < tc.row_end && col < a.N) {
+            const int64_t crow = a.c_rows ? a.c_rows[p] : p;
+            res[i][ps] = *reinterpret_cast<const u32x4_t *>(static_cast<const bf16_t *>(a.residual) +
+                                                            crow * a.ldc + col);
+          }
+        }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       float scale = 1.0f;
@@ -187,27 +207,35 @@ __device__ __forceinline__ void mfma_epilogue(const GemmArgs &a, const TileCoord
           *reinterpret_cast<uint2 *>(stage + frag_row * kPitch + lcol * 2) = pk;
         }
       }
-#pragma unroll 4
-      for (int r0 = 0; r0 < 32; r0 += kRowsPerPass) {
-        const int row = r0 + sub;
-        const int64_t p = tc.row0 + wm * WTM + i * 32 + row;
-        if (row < 32 && p < tc.row_end && col < a.N) {
-          const int64_t crow = a.c_rows ? a.c_rows[p] : p;
-          uint4 v = *reinterpret_cast<const uint4 *>(stage + row * kPitch + chunk * 16);
-          if (EPI == kEpiRowScaleResidual) {
-            // skip connection: the block's input row, in the output's layout, is added to the
-            // (already rounded) branch output here, where a lane holds 8 consecutive columns
-            const u32x4_t res = *reinterpret_cast<const u32x4_t *>(
-                static_cast<const bf16_t *>(a.residual) + crow * a.ldc + col);
+      if constexpr (EPI == kEpiRowScaleResidual) {
+#pragma unroll
+        for (int ps = 0; ps < kPasses; ++ps) {
+          const int row = ps * kRowsPerPass + sub;
+          const int64_t p = tc.row0 + wm * WTM + i * 32 + row;
+          if (row < 32 && p < tc.row_end && col < a.N) {
+            const int64_t crow = a.c_rows ? a.c_rows[p] : p;
+            uint4 v = *reinterpret_cast<const uint4 *>(stage + row * kPitch + chunk * 16);
+            // added to the (already rounded) branch output here, where a lane holds 8 consecutive columns
             unsigned int *vw = &v.x;
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-              const float lo = __uint_as_float(vw[w] << 16) + __uint_as_float(res[w] << 16);
-              const float hi = __uint_as_float(vw[w] & 0xFFFF0000u) + __uint_as_float(res[w] & 0xFFFF0000u);
+              const float lo = __uint_as_float(vw[w] << 16) + __uint_as_float(res[i][ps][w] << 16);
+              const float hi = __uint_as_float(vw[w] & 0xFFFF0000u) + __uint_as_float(res[i][ps][w] & 0xFFFF0000u);
               vw[w] = pack_bf16x2(lo, hi);
             }
+            *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.C) + crow * a.ldc + col) = v;
           }
-          *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.C) + crow * a.ldc + col) = v;
+        }
+      } else {
+#pragma unroll 4
+        for (int r0 = 0; r0 < 32; r0 += kRowsPerPass) {
+          const int row = r0 + sub;
+          const int64_t p = tc.row0 + wm * WTM + i * 32 + row;
+          if (row < 32 && p < tc.row_end && col < a.N) {
+            const int64_t crow = a.c_rows ? a.c_rows[p] : p;
+            const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * kPitch + chunk * 16);
+            *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.C) + crow * a.ldc + col) = v;
+          }
         }
       }
     }
