@@ -27,6 +27,8 @@ Readings of the paper taken here (each is also listed in the design notes):
     are indicator sums like Eq. (11); dt_bias is one shared vector.
   * Top-K picks on logits, descending, lowest expert index on ties.
   * Eq. (16): per-layer term, F normalised by N*K, expectation over the call's tokens.
+  * Eq. (14)/(15): the FFN-MoE layer takes both the TopK set and the weights R_i from the
+    preceding RoM layer's router; its experts are SwiGLU MLPs with SiLU as the gate activation.
   * The pre-norm is RMSNorm with a learned scale and an eps inside the square root (the
     paper cites it without a formula or an eps); the skip adds the block's own input.
 """
@@ -333,3 +335,35 @@ def rom_stack_forward(x, layers, top_k, gate_mode=0, eps=1e-5, conv_states=None,
         results.append(res)
         h = res["out"]
     return h, results
+
+
+# --------------------------------------------------------------------------
+# FFN-MoE with the routing decision of the preceding RoM layer (appendix, Eq. (14), (15))
+# --------------------------------------------------------------------------
+def swiglu_expert(x, w_gate_up, w_down):
+    """f(x) = W_down (SiLU(W_gate x) * (W_up x)) for one feed-forward SwiGLU expert.
+    x [n, D_m]; w_gate_up [2*D_f, D_m] (rows [0, D_f) gate, rows [D_f, 2*D_f) up); w_down [D_m, D_f]."""
+    x = np.asarray(x, F64)
+    w_gate_up = np.asarray(w_gate_up, F64)
+    d_f = w_gate_up.shape[0] // 2
+    h = x @ w_gate_up.T
+    return (silu(h[:, :d_f]) * h[:, d_f:]) @ np.asarray(w_down, F64).T
+
+
+def ffn_moe_forward(x, w_gate_up, w_down, idx, gate, norm_w=None, eps=1e-5, skip=False):
+    """Y[n] = sum_i R_i[n] * 1[i in TopK[n]] * f_i(X[n])   (Eq. (14), (15)): no router of its own,
+    the experts idx [N, K] and weights gate [N, K] are those of the RoM layer in front of it.
+    x [N, D_m]; w_gate_up [E, 2*D_f, D_m]; w_down [E, D_m, D_f].
+    norm_w: the experts see RMSNorm(x) (pre-norm); skip: x is added to the result."""
+    x = np.asarray(x, F64)
+    xin = x if norm_w is None else rms_norm(x, norm_w, eps)
+    idx = np.asarray(idx)
+    gate = np.asarray(gate, F64)
+    n_exp = np.asarray(w_gate_up).shape[0]
+    y = np.zeros_like(x)
+    for k in range(idx.shape[1]):
+        for i in range(n_exp):
+            rows = np.nonzero(idx[:, k] == i)[0]
+            if rows.size:
+                y[rows] += gate[rows, k:k + 1] * swiglu_expert(xin[rows], w_gate_up[i], w_down[i])
+    return x + y if skip else y

@@ -571,6 +571,56 @@ def test_stack_is_the_composition_of_blocks_with_per_layer_state():
     np.testing.assert_array_equal(out2[:, :6], out[:, :6])
 
 
+def test_ffn_moe_against_library_mlp_and_brute_force():
+    """Eq. (14)/(15): one expert with weight 1 is a dense SwiGLU MLP from library routines; the routed
+    form equals a scalar-loop evaluation of every expert times its indicator and weight."""
+    rng = np.random.default_rng(31)
+    n, d_m, d_f, n_exp = 11, 6, 10, 4
+    x = rng.standard_normal((n, d_m))
+    wgu = rng.standard_normal((n_exp, 2 * d_f, d_m)) * 0.5
+    wd = rng.standard_normal((n_exp, d_m, d_f)) * 0.5
+    xt = torch.from_numpy(x)
+    gate_w, up_w = torch.from_numpy(wgu[2, :d_f]), torch.from_numpy(wgu[2, d_f:])
+    want = F.linear(F.silu(F.linear(xt, gate_w)) * F.linear(xt, up_w), torch.from_numpy(wd[2])).numpy()
+    idx1 = np.full((n, 1), 2)
+    got = O.ffn_moe_forward(x, wgu, wd, idx1, np.ones((n, 1)))
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+    # swapping the gate and up halves changes the result (SiLU sits on the first half)
+    swapped = np.concatenate([wgu[:, d_f:], wgu[:, :d_f]], axis=1)
+    assert np.max(np.abs(O.ffn_moe_forward(x, swapped, wd, idx1, np.ones((n, 1))) - want)) > 1e-3
+
+    logits = rng.standard_normal((n, n_exp))
+    for K, mode in ((1, 0), (2, 0), (3, 1)):
+        idx = O.topk_select(logits, K)
+        gate = O.gate_weights(logits, idx, mode)
+        got = O.ffn_moe_forward(x, wgu, wd, idx, gate)
+        want = np.zeros((n, d_m))
+        for t in range(n):
+            for i in range(n_exp):
+                r = sum(gate[t, k] for k in range(K) if idx[t, k] == i)      # R_i * indicator
+                if r == 0.0:
+                    continue
+                hid = [0.0] * d_f
+                for f in range(d_f):
+                    a = sum(wgu[i, f, d] * x[t, d] for d in range(d_m))
+                    b = sum(wgu[i, d_f + f, d] * x[t, d] for d in range(d_m))
+                    hid[f] = a / (1.0 + np.exp(-a)) * b
+                for d in range(d_m):
+                    want[t, d] += r * sum(wd[i, d, f] * hid[f] for f in range(d_f))
+        np.testing.assert_allclose(got, want, rtol=1e-11, atol=1e-12)
+    # pre-norm and skip: experts see the normalised rows, the raw rows are added
+    nw = rng.uniform(0.5, 1.5, d_m)
+    xn = F.rms_norm(xt, (d_m,), torch.from_numpy(nw), eps=1e-5).numpy()
+    np.testing.assert_allclose(O.ffn_moe_forward(x, wgu, wd, idx, gate, nw, 1e-5, skip=True),
+                               x + O.ffn_moe_forward(xn, wgu, wd, idx, gate), rtol=1e-12, atol=1e-13)
+    # all experts identical and weights summing to one: routing cannot matter
+    same_gu, same_d = np.repeat(wgu[:1], n_exp, 0), np.repeat(wd[:1], n_exp, 0)
+    idx = O.topk_select(logits, 2)
+    gate = O.gate_weights(logits, idx, 1)
+    np.testing.assert_allclose(O.ffn_moe_forward(x, same_gu, same_d, idx, gate),
+                               O.swiglu_expert(x, wgu[0], wd[0]), rtol=1e-12, atol=1e-13)
+
+
 def test_softplus_and_silu_against_library():
     v = np.linspace(-40, 40, 161)
     assert np.allclose(O.softplus(v), F.softplus(torch.from_numpy(v), threshold=1e9).numpy(), rtol=1e-13)
