@@ -232,6 +232,41 @@ ROM_API int rom_stack_step(const rom_dims *dims, const rom_block *blocks, int n_
                    const void *x, int64_t B, float *conv_state, float *ssm_state,
                    void *out, void *tmp, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* ---- FFN-MoE layer that shares the routing decision of the RoM layer in front of it (appendix,
+ * the two equations after the architectures overview):
+ *   y[n, :] = sum_k gate[n, k] * f_{e(n,k)}(x[n, :]),   f_i(v) = W_down,i (SiLU(W_gate,i v) * (W_up,i v))
+ * It has no router: the expert of every (token, k) slot and its weight come from the preceding
+ * rom_route / rom_layer_forward / rom_block_forward call over the same N tokens, as the grouping
+ * that call produced.  Optionally the experts see RMSNorm(x) (pre_norm; the norm's scale must
+ * then be folded into w_gate_up with rom_ffn_fold_norm) and x is added to the result (add_skip). */
+typedef struct rom_ffn_weights {
+  const void *w_gate_up;  /* T [E, 2*d_ff, d_model]; rows [0, d_ff) gate, rows [d_ff, 2*d_ff) up */
+  const void *w_down;     /* T [E, d_model, d_ff]                                              */
+} rom_ffn_weights;
+
+/* Workspace bytes of rom_ffn_moe_forward for N tokens (0 if dims / d_ff are unsupported:
+ * d_ff must be a positive multiple of 16).  Only d_model, n_experts, top_k and dtype of dims
+ * matter, but dims must be a valid layer shape. */
+ROM_API size_t rom_ffn_workspace_bytes(const rom_dims *dims, int32_t d_ff, int64_t N);
+
+/* w_gate_up_folded[e, o, d] = w_gate_up[e, o, d] * norm_weight[d] (device; may be in place). */
+ROM_API int rom_ffn_fold_norm(const rom_dims *dims, int32_t d_ff, const void *w_gate_up,
+                      const float *norm_weight, void *w_gate_up_folded, void *hip_stream);
+
+/*   x        T   [N, d_model];  out  T [N, d_model], must not alias x
+ *   offsets  i32 [E+1], perm i32 [N*K], inv_perm i32 [N*K], gate f32 [N, K]: as written by
+ *            rom_route, or the workspace regions of the same names after a layer / block call
+ *            (that workspace must stay untouched until this call has run)
+ *   pre_norm != 0: experts see x / sqrt(mean(x^2) + eps) * norm_weight (scale folded, see above)
+ *   add_skip != 0: out = x + y
+ *   ws       rom_ffn_workspace_bytes(dims, d_ff, N) bytes, 256-byte aligned, distinct from the
+ *            workspace that holds offsets / perm / inv_perm / gate
+ * N == 0 is a successful no-op. */
+ROM_API int rom_ffn_moe_forward(const rom_dims *dims, int32_t d_ff, const rom_ffn_weights *w,
+                        int pre_norm, float eps, int add_skip, const void *x, int64_t N,
+                        const int32_t *offsets, const int32_t *perm, const int32_t *inv_perm,
+                        const float *gate, void *out, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Static description of an error code. */
 ROM_API const char *rom_strerror(int code);
 

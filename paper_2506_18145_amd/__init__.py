@@ -6,12 +6,16 @@ the layer runs in the HIP kernels behind the C ABI declared in include/rom.h.
 from .binding import (  # noqa: F401
     RomDims,
     RomError,
+    RomFfnMoe,
     RomLayer,
     RomStack,
     load_library,
     rom_balance_stats,
     rom_block_forward,
     rom_block_step,
+    rom_ffn_fold_norm,
+    rom_ffn_moe_forward,
+    rom_ffn_workspace_bytes,
     rom_fold_norm,
     rom_stack_forward,
     rom_stack_step,

@@ -35,6 +35,10 @@ class _RomBlock(ctypes.Structure):
     _fields_ = [("w", _RomWeights), ("norm_weight", ctypes.c_void_p)]
 
 
+class _RomFfnWeights(ctypes.Structure):
+    _fields_ = [("w_gate_up", ctypes.c_void_p), ("w_down", ctypes.c_void_p)]
+
+
 class _RomWsLayout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in (
         "total_bytes", "expert_idx", "gate", "counts", "offsets", "perm", "inv_perm", "logits", "xz",
@@ -80,6 +84,13 @@ def load_library() -> ctypes.CDLL:
     lib.rom_stack_step.restype = ctypes.c_int
     lib.rom_stack_step.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomBlock), ctypes.c_int, F32, P,
                                    I64, P, P, P, P, P, SZ, P]
+    lib.rom_ffn_workspace_bytes.restype = SZ
+    lib.rom_ffn_workspace_bytes.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, I64]
+    lib.rom_ffn_fold_norm.restype = ctypes.c_int
+    lib.rom_ffn_fold_norm.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, P, P, P, P]
+    lib.rom_ffn_moe_forward.restype = ctypes.c_int
+    lib.rom_ffn_moe_forward.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, ctypes.POINTER(_RomFfnWeights),
+                                        ctypes.c_int, F32, ctypes.c_int, P, I64, P, P, P, P, P, P, SZ, P]
     lib.rom_strerror.restype = ctypes.c_char_p
     lib.rom_strerror.argtypes = [ctypes.c_int]
     lib.rom_profile_enable.restype = ctypes.c_int
@@ -210,6 +221,25 @@ def rom_stack_step(dims, blocks, eps, x, B, conv_state, ssm_state, out, tmp, ws)
         ctypes.byref(dims), blocks, len(blocks), eps, _ptr(x), B, _ptr(conv_state), _ptr(ssm_state),
         _ptr(out), _ptr(tmp), _ptr(ws), _nbytes(ws), _stream())
     _check(code, "rom_stack_step")
+
+
+def rom_ffn_workspace_bytes(dims, d_ff: int, n_tokens: int) -> int:
+    return int(load_library().rom_ffn_workspace_bytes(ctypes.byref(dims), d_ff, n_tokens))
+
+
+def rom_ffn_fold_norm(dims, d_ff, w_gate_up, norm_weight, w_gate_up_folded):
+    _check(load_library().rom_ffn_fold_norm(ctypes.byref(dims), d_ff, _ptr(w_gate_up), _ptr(norm_weight),
+                                            _ptr(w_gate_up_folded), _stream()), "rom_ffn_fold_norm")
+
+
+def rom_ffn_moe_forward(dims, d_ff, w_gate_up, w_down, pre_norm, eps, add_skip, x, n_tokens, offsets, perm,
+                        inv_perm, gate, out, ws):
+    w = _RomFfnWeights(_ptr(w_gate_up), _ptr(w_down))
+    code = load_library().rom_ffn_moe_forward(
+        ctypes.byref(dims), d_ff, ctypes.byref(w), int(bool(pre_norm)), eps, int(bool(add_skip)), _ptr(x),
+        n_tokens, _ptr(offsets), _ptr(perm), _ptr(inv_perm), _ptr(gate), _ptr(out), _ptr(ws), _nbytes(ws),
+        _stream())
+    _check(code, "rom_ffn_moe_forward")
 
 
 def rom_set_segments(n_segments: int) -> None:
@@ -417,4 +447,40 @@ class RomStack:
             out = torch.empty_like(x)
         rom_stack_step(self.dims, self.blocks, self.eps, x, B, conv_state, ssm_state, out, self._scratch(x),
                        self.layers[0].workspace(max(B, 1), 1))
+        return out
+
+
+class RomFfnMoe:
+    """An FFN-MoE layer (SwiGLU experts) that runs on the routing decision of a RomLayer call."""
+
+    def __init__(self, layer: RomLayer, d_ff: int, weights, eps: float = 1e-5):
+        self.layer, self.dims, self.d_ff, self.eps = layer, layer.dims, d_ff, eps
+        self.device = layer.device
+        conv = lambda a, dt: (a if isinstance(a, torch.Tensor) else torch.from_numpy(a)).to(dt).to(self.device).contiguous()
+        self.w_gate_up = conv(weights["w_gate_up"], layer.tdtype)
+        self.w_down = conv(weights["w_down"], layer.tdtype)
+        self.norm_w = conv(weights["norm_w"], torch.float32) if weights.get("norm_w") is not None else None
+        self._folded: Optional[torch.Tensor] = None
+        self._ws: Optional[torch.Tensor] = None
+
+    def folded(self) -> torch.Tensor:
+        if self._folded is None:
+            self._folded = torch.empty_like(self.w_gate_up)
+            rom_ffn_fold_norm(self.dims, self.d_ff, self.w_gate_up, self.norm_w, self._folded)
+        return self._folded
+
+    def forward(self, x: torch.Tensor, routing, pre_norm: bool = False, add_skip: bool = False,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """x [N, d_model] (or [B, L, d_model]); routing: mapping with offsets, perm, inv_perm, gate."""
+        n = x.numel() // self.dims.d_model
+        need = rom_ffn_workspace_bytes(self.dims, self.d_ff, max(n, 1))
+        if need == 0:
+            raise RomError("rom_ffn_workspace_bytes returned 0: unsupported dims or d_ff")
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        if out is None:
+            out = torch.empty_like(x)
+        rom_ffn_moe_forward(self.dims, self.d_ff, self.folded() if pre_norm else self.w_gate_up, self.w_down,
+                            pre_norm, self.eps, add_skip, x, n, routing["offsets"], routing["perm"],
+                            routing["inv_perm"], routing["gate"], out, self._ws)
         return out

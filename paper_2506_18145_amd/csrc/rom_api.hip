@@ -530,6 +530,37 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   return ROM_OK;
 }
 
+// ---------------------------------------------------------------- FFN-MoE (Eq. (14), (15))
+struct FfnPlan {
+  size_t total, tok_of_pos, rstd, h, a, op_sorted;
+};
+
+int check_ffn(const rom_dims *d, int32_t d_ff) {
+  const int rc = check_dims(d);
+  if (rc != ROM_OK) return rc;
+  if (d_ff <= 0) return ROM_E_INVAL;
+  if (d_ff % 16 != 0) return ROM_E_UNSUPPORTED;
+  return ROM_OK;
+}
+
+FfnPlan make_ffn_plan(const rom_dims *d, int32_t d_ff, int64_t n_tok) {
+  FfnPlan p;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off += (bytes + kAlign - 1) / kAlign * kAlign;
+    return at;
+  };
+  const size_t S = static_cast<size_t>(n_tok) * d->top_k, b = d->dtype == ROM_DTYPE_BF16 ? 2 : 4;
+  p.tok_of_pos = take(S * 4);
+  p.rstd = take(S * 4);
+  p.h = take(S * 2 * d_ff * b);
+  p.a = take(S * d_ff * b);
+  p.op_sorted = d->top_k > 1 ? take(S * d->d_model * b) : kNone;
+  p.total = off;
+  return p;
+}
+
 }  // namespace
 }  // namespace rom
 
@@ -674,6 +705,81 @@ int rom_stack_forward(const rom_dims *dims, const rom_block *blocks, int n_layer
                       static_cast<hipStream_t>(hip_stream), &blk);
     if (rc != ROM_OK) return rc;
     src = dst;
+  }
+  return ROM_OK;
+}
+
+size_t rom_ffn_workspace_bytes(const rom_dims *dims, int32_t d_ff, int64_t N) {
+  if (check_ffn(dims, d_ff) != ROM_OK || N < 0) return 0;
+  return make_ffn_plan(dims, d_ff, N > 0 ? N : 1).total;
+}
+
+int rom_ffn_fold_norm(const rom_dims *dims, int32_t d_ff, const void *w_gate_up, const float *norm_weight,
+                      void *w_gate_up_folded, void *hip_stream) {
+  int rc = check_ffn(dims, d_ff);
+  if (rc != ROM_OK) return rc;
+  if (!w_gate_up || !norm_weight || !w_gate_up_folded) return ROM_E_INVAL;
+  const int64_t rows = static_cast<int64_t>(dims->n_experts) * 2 * d_ff;
+  const int64_t n = rows * dims->d_model;
+  const dim3 grid(static_cast<unsigned>(ceil_div(n, 256)));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (dims->dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL(fold_cols_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(w_gate_up),
+                       norm_weight, static_cast<bf16_t *>(w_gate_up_folded), rows, dims->d_model);
+  else
+    hipLaunchKernelGGL(fold_cols_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(w_gate_up),
+                       norm_weight, static_cast<float *>(w_gate_up_folded), rows, dims->d_model);
+  return hipGetLastError() == hipSuccess ? ROM_OK : ROM_E_HIP;
+}
+
+int rom_ffn_moe_forward(const rom_dims *dims, int32_t d_ff, const rom_ffn_weights *w, int pre_norm, float eps,
+                        int add_skip, const void *x, int64_t N, const int32_t *offsets, const int32_t *perm,
+                        const int32_t *inv_perm, const float *gate, void *out, void *ws, size_t ws_bytes,
+                        void *hip_stream) {
+  int rc = check_ffn(dims, d_ff);
+  if (rc != ROM_OK) return rc;
+  if (!w || !w->w_gate_up || !w->w_down || !aligned16(w->w_gate_up) || !aligned16(w->w_down)) return ROM_E_INVAL;
+  if (N < 0 || (pre_norm && !(eps >= 0.0f))) return ROM_E_INVAL;
+  if (N == 0) return ROM_OK;
+  if (!x || !out || x == out || !offsets || !perm || !inv_perm || !gate || !ws) return ROM_E_INVAL;
+  if (!aligned16(x) || !aligned16(out) || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return ROM_E_INVAL;
+  if (N * dims->top_k > (1ll << 30)) return ROM_E_UNSUPPORTED;
+  const FfnPlan p = make_ffn_plan(dims, d_ff, N);
+  if (ws_bytes < p.total) return ROM_E_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char *base = static_cast<char *>(ws);
+  const int K = dims->top_k, E = dims->n_experts, Dm = dims->d_model;
+  const int64_t S = N * K;
+  int32_t *tok_of_pos = reinterpret_cast<int32_t *>(base + p.tok_of_pos);
+  float *rstd = pre_norm ? reinterpret_cast<float *>(base + p.rstd) : nullptr;
+  ROM_TRY(launch_ffn_prep(dims->dtype, perm, K, S, x, Dm, eps, tok_of_pos, rstd, s));
+
+  // gate | up projection of every slot by its expert, rows kept in sorted order
+  GemmArgs ga;
+  memset(&ga, 0, sizeof(ga));
+  ga.dtype = dims->dtype;
+  ga.A = x; ga.lda = Dm; ga.a_rows = tok_of_pos; ga.a_span = N * Dm;
+  ga.W = w->w_gate_up; ga.N = 2 * d_ff; ga.K = Dm;
+  ga.offsets = offsets; ga.n_groups = E; ga.M = S;
+  ga.C = base + p.h; ga.ldc = 2 * d_ff;
+  ga.row_scale = rstd;                      // pre-norm: the weight's columns carry the norm's scale
+  ROM_TRY(launch_grouped_gemm(ga, s));
+  ROM_TRY(launch_swiglu(dims->dtype, base + p.h, base + p.a, S, d_ff, s));
+
+  // down projection, weighted by the router's R_i and brought back to token order
+  memset(&ga, 0, sizeof(ga));
+  ga.dtype = dims->dtype;
+  ga.A = base + p.a; ga.lda = d_ff; ga.a_span = S * d_ff;
+  ga.W = w->w_down; ga.N = Dm; ga.K = d_ff;
+  ga.offsets = offsets; ga.n_groups = E; ga.M = S;
+  if (K > 1) {
+    ga.C = base + p.op_sorted; ga.ldc = Dm;
+    ROM_TRY(launch_grouped_gemm(ga, s));
+    ROM_TRY(launch_combine(dims->dtype, base + p.op_sorted, inv_perm, gate, out, N, K, Dm, add_skip ? x : nullptr, s));
+  } else {
+    ga.C = out; ga.ldc = Dm; ga.c_rows = tok_of_pos; ga.row_scale = gate;
+    if (add_skip) ga.residual = x;
+    ROM_TRY(launch_grouped_gemm(ga, s));
   }
   return ROM_OK;
 }

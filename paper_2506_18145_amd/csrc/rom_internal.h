@@ -113,4 +113,11 @@ hipError_t launch_combine(int dtype, const void *op, const int32_t *inv_perm, co
                           void *out, int64_t n_tokens, int top_k, int d_model, const void *residual,
                           hipStream_t s);
 
+// ---------------------------------------------------------------- FFN-MoE (Eq. (14), (15))
+// a[p, :] = SiLU(h[p, :d_ff]) * h[p, d_ff:]   (h T [n_rows, 2*d_ff], a T [n_rows, d_ff]; d_ff % 8 == 0)
+hipError_t launch_swiglu(int dtype, const void *h, void *a, int64_t n_rows, int d_ff, hipStream_t s);
+// tok_of_pos[p] = perm[p] / K; rstd_sorted (may be NULL) [p] = 1 / sqrt(mean(x[tok_of_pos[p]]^2) + eps)
+hipError_t launch_ffn_prep(int dtype, const int32_t *perm, int top_k, int64_t n_slots, const void *x,
+                           int d_model, float eps, int32_t *tok_of_pos, float *rstd_sorted, hipStream_t s);
+
 }  // namespace rom

@@ -649,6 +649,56 @@ __global__ __launch_bounds__(256) void combine_kernel(const T *__restrict__ op,
   o.store(out + n * d_model + c0);
 }
 
+// ------------------------------------------------------------------ FFN-MoE helpers, Eq. (14), (15)
+// a[p, f] = SiLU(h[p, f]) * h[p, d_ff + f]: the SwiGLU of one expert's gate | up projection row
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_kernel(const T *__restrict__ h, T *__restrict__ a,
+                                                     int64_t n_rows, int d_ff) {
+  constexpr int V = Chunk<T>::kElems;
+  const int groups = d_ff / V;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (idx >= n_rows * groups) return;
+  const int64_t row = idx / groups;
+  const int c0 = static_cast<int>(idx % groups) * V;
+  Chunk<T> g, u, o;
+  g.load(h + row * 2 * d_ff + c0);
+  u.load(h + row * 2 * d_ff + d_ff + c0);
+#pragma unroll
+  for (int i = 0; i < V / 2; ++i)
+    o.set_pair(i, silu_f32(g.get(2 * i)) * u.get(2 * i), silu_f32(g.get(2 * i + 1)) * u.get(2 * i + 1));
+  o.store(a + row * d_ff + c0);
+}
+
+// tok_of_pos[p] = perm[p] / K for the sorted positions of a routing decision made elsewhere
+__global__ __launch_bounds__(256) void tok_of_pos_kernel(const int32_t *__restrict__ perm, int top_k,
+                                                         int64_t n_slots, int32_t *__restrict__ tok_of_pos) {
+  const int64_t p = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (p < n_slots) tok_of_pos[p] = perm[p] / top_k;
+}
+
+// one wavefront per sorted position: rstd_sorted[p] = 1 / sqrt(mean(x[tok_of_pos[p], :]^2) + eps)
+template <typename T>
+__global__ __launch_bounds__(256) void rstd_sorted_kernel(const T *__restrict__ x, int d_model,
+                                                          const int32_t *__restrict__ tok_of_pos,
+                                                          int64_t n_slots, float eps,
+                                                          float *__restrict__ rstd_sorted) {
+  constexpr int V = Chunk<T>::kElems;
+  const int lane = threadIdx.x & 63;
+  const int64_t p = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) >> 6;
+  if (p >= n_slots) return;                       // whole wavefront
+  const T *row = x + static_cast<int64_t>(tok_of_pos[p]) * d_model;
+  float ss = 0.0f;
+  for (int c0 = lane * V; c0 < d_model; c0 += 64 * V) {
+    Chunk<T> c;
+    c.load(row + c0);
+#pragma unroll
+    for (int i = 0; i < V; ++i) ss = fmaf(c.get(i), c.get(i), ss);
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) ss += __shfl_xor(ss, o, 64);
+  if (lane == 0) rstd_sorted[p] = 1.0f / sqrtf(ss / static_cast<float>(d_model) + eps);
+}
+
 inline dim3 grid1d(int64_t work, int block) { return dim3(static_cast<unsigned>(ceil_div(work, block))); }
 
 }  // namespace
@@ -677,6 +727,33 @@ hipError_t launch_slot_sum(int src_is_f32, int dst_is_f32, const void *src, int6
   else if (dst_is_f32) ROM_SS(bf16_t, float);
   else ROM_SS(bf16_t, bf16_t);
 #undef ROM_SS
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu(int dtype, const void *h, void *a, int64_t n_rows, int d_ff, hipStream_t s) {
+  const int V = dtype == ROM_DTYPE_BF16 ? 8 : 4;
+  const dim3 grid = grid1d(n_rows * (d_ff / V), 256);
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL(swiglu_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(h),
+                       static_cast<bf16_t *>(a), n_rows, d_ff);
+  else
+    hipLaunchKernelGGL(swiglu_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(h),
+                       static_cast<float *>(a), n_rows, d_ff);
+  return hipGetLastError();
+}
+
+hipError_t launch_ffn_prep(int dtype, const int32_t *perm, int top_k, int64_t n_slots, const void *x,
+                           int d_model, float eps, int32_t *tok_of_pos, float *rstd_sorted, hipStream_t s) {
+  hipLaunchKernelGGL(tok_of_pos_kernel, grid1d(n_slots, 256), dim3(256), 0, s, perm, top_k, n_slots, tok_of_pos);
+  if (rstd_sorted) {
+    const dim3 grid = grid1d(n_slots * 64, 256);
+    if (dtype == ROM_DTYPE_BF16)
+      hipLaunchKernelGGL(rstd_sorted_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(x),
+                         d_model, tok_of_pos, n_slots, eps, rstd_sorted);
+    else
+      hipLaunchKernelGGL(rstd_sorted_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(x),
+                         d_model, tok_of_pos, n_slots, eps, rstd_sorted);
+  }
   return hipGetLastError();
 }
 

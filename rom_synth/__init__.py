@@ -11,6 +11,7 @@ from .configs import (  # noqa: F401
     get_config,
     make_weights,
     make_stack_weights,
+    make_ffn_weights,
     make_input,
     make_states,
     make_step_inputs,

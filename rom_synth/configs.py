@@ -119,7 +119,8 @@ def _store(cfg: RomConfig, a: np.ndarray) -> np.ndarray:
 
 
 # tensor ids (seed = 1000 * cfg_id + id)
-_T_X, _T_WR, _T_WIN, _T_CW, _T_CB, _T_WX, _T_WDT, _T_DTB, _T_WOUT, _T_CS, _T_SS, _T_XS, _T_NORM = range(1, 14)
+(_T_X, _T_WR, _T_WIN, _T_CW, _T_CB, _T_WX, _T_WDT, _T_DTB, _T_WOUT, _T_CS, _T_SS, _T_XS, _T_NORM, _T_FGU,
+ _T_FDN, _T_FNORM) = range(1, 17)
 
 
 def make_weights(cfg: RomConfig) -> Dict[str, Optional[np.ndarray]]:
@@ -148,6 +149,17 @@ def make_weights(cfg: RomConfig) -> Dict[str, Optional[np.ndarray]]:
     # [0.7, 1.3] here so that a missing or misplaced scale cannot hide
     w["norm_w"] = _rng(cfg, _T_NORM).uniform(0.7, 1.3, (Dm,)).astype(np.float32)
     return w
+
+
+def make_ffn_weights(cfg: RomConfig, d_ff: int) -> Dict[str, np.ndarray]:
+    """Parameters of an FFN-MoE layer with cfg's experts: w_gate_up [E, 2*d_ff, d_model] (gate rows
+    first), w_down [E, d_model, d_ff], norm_w [d_model] (fp32, scale of its pre-norm)."""
+    E, Dm = cfg.n_experts, cfg.d_model
+    return {
+        "w_gate_up": _store(cfg, _normal(cfg, _T_FGU, (E, 2 * d_ff, Dm), cfg.weight_std)),
+        "w_down": _store(cfg, _normal(cfg, _T_FDN, (E, Dm, d_ff), cfg.weight_std)),
+        "norm_w": _rng(cfg, _T_FNORM).uniform(0.7, 1.3, (Dm,)).astype(np.float32),
+    }
 
 
 def make_stack_weights(cfg: RomConfig, n_layers: int):

@@ -40,6 +40,7 @@ def test_struct_sizes_match_header():
     assert ctypes.sizeof(binding._RomWeights) == 11 * ctypes.sizeof(ctypes.c_void_p)
     assert ctypes.sizeof(binding._RomWsLayout) == 14 * ctypes.sizeof(ctypes.c_size_t)
     assert ctypes.sizeof(binding._RomBlock) == 12 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(binding._RomFfnWeights) == 2 * ctypes.sizeof(ctypes.c_void_p)
 
 
 def test_workspace_bytes_and_layout(lib):
@@ -209,3 +210,30 @@ def test_block_and_stack_arguments_are_checked_before_any_launch(lib):
     assert call(blocks, 2, addr + 2048) == -1
     assert lib.rom_stack_step(ctypes.byref(d), blocks, 2, F(1e-5), addr, 4, None, None, addr + 4096,
                               addr + 2048, addr, 4096, None) == -1
+
+
+def test_ffn_moe_arguments_and_workspace(lib):
+    from paper_2506_18145_amd import binding
+    d = _dims(n_experts=4, top_k=2)
+    assert binding.rom_ffn_workspace_bytes(d, 24, 8) == 0            # d_ff not a multiple of 16
+    assert binding.rom_ffn_workspace_bytes(d, 0, 8) == 0
+    assert binding.rom_ffn_workspace_bytes(_dims(d_state=8), 32, 8) == 0
+    small, big = binding.rom_ffn_workspace_bytes(d, 32, 8), binding.rom_ffn_workspace_bytes(d, 32, 64)
+    # slots x (gate|up row + activated row + per-expert output row) at least
+    assert 0 < small < big and big >= 64 * 2 * (2 * 32 + 32 + 64) * 4
+    buf = ctypes.create_string_buffer(8192 + 256)
+    addr = (ctypes.addressof(buf) + 255) // 256 * 256
+    w = binding._RomFfnWeights(addr, addr)
+    F = ctypes.c_float
+    call = lambda dims, d_ff, wp, x, out, n, ws, nbytes, offs=addr: lib.rom_ffn_moe_forward(
+        ctypes.byref(dims), d_ff, wp, 1, F(1e-5), 1, x, n, offs, addr, addr, addr, out, ws, nbytes, None)
+    assert call(d, 32, ctypes.byref(w), addr, addr + 4096, 0, addr, 4096) == 0        # no tokens
+    assert call(d, 24, ctypes.byref(w), addr, addr + 4096, 8, addr, 4096) == -3
+    assert call(d, 32, None, addr, addr + 4096, 8, addr, 4096) == -1
+    assert call(d, 32, ctypes.byref(w), addr, addr, 8, addr, 4096) == -1              # out aliases x
+    assert call(d, 32, ctypes.byref(w), addr, addr + 4096, 8, addr, 4096, offs=None) == -1
+    assert call(d, 32, ctypes.byref(w), addr, addr + 4096, 8, addr + 8, 4096) == -1   # misaligned workspace
+    assert call(d, 32, ctypes.byref(w), addr, addr + 4096, 8, addr, 4096) == -2       # workspace too small
+    assert lib.rom_ffn_moe_forward(ctypes.byref(d), 32, ctypes.byref(w), 1, F(-1.0), 1, addr, 8, addr, addr, addr,
+                                   addr, addr + 4096, addr, 4096, None) == -1         # negative eps
+    assert lib.rom_ffn_fold_norm(ctypes.byref(d), 32, None, addr, addr, None) == -1

@@ -7,8 +7,9 @@ import pytest
 import torch
 
 from oracle import rom_oracle as O
-from paper_2506_18145_amd import RomLayer, RomStack
-from rom_synth import RomConfig, get_config, make_input, make_stack_weights, make_states, make_weights
+from paper_2506_18145_amd import RomFfnMoe, RomLayer, RomStack
+from rom_synth import (RomConfig, get_config, make_ffn_weights, make_input, make_stack_weights, make_states,
+                       make_weights)
 
 from gpu_util import BLOCK_EPS, MARGIN, TOL, check_routing, compare_layer, rel_err, run_layer, to_np
 
@@ -412,3 +413,57 @@ def test_stack_forward_and_step(dtype):
         h = ly.block_step(h, conv_s[j], ssm_s[j], eps=BLOCK_EPS)
     torch.cuda.synchronize()
     assert torch.equal(h, o_stack) and torch.equal(conv_a, conv_s) and torch.equal(ssm_a, ssm_s)
+
+
+# ---------------------------------------------------------------------------------------------
+# FFN-MoE on the preceding RoM layer's routing decision
+# ---------------------------------------------------------------------------------------------
+def _ffn_case(cfg, d_ff, pre_norm, add_skip, via_forward):
+    """Routes with the GPU (rom_route, or a whole block call whose workspace then holds the
+    grouping), runs the FFN-MoE layer on that decision, and compares with the oracle fed the
+    GPU's own expert choice (bit-checked against the oracle's outside the margin band)."""
+    w = make_weights(cfg)
+    fw = make_ffn_weights(cfg, d_ff)
+    x = make_input(cfg)
+    layer = RomLayer(cfg, w)
+    ffn = RomFfnMoe(layer, d_ff, fw, eps=BLOCK_EPS)
+    B, L = cfg.batch, cfg.seq_len
+    N = B * L
+    xd = layer.to_device(x)
+    if via_forward:
+        layer.forward(xd)
+        routing = {k: layer.ws_view(k, B, L) for k in ("offsets", "perm", "inv_perm", "gate", "expert_idx",
+                                                       "counts", "logits")}
+    else:
+        routing = layer.route(xd.view(N, -1))
+    out = ffn.forward(xd, routing, pre_norm=pre_norm, add_skip=add_skip)
+    torch.cuda.synchronize()
+    gpu = {k: to_np(routing[k]) for k in ("expert_idx", "gate", "counts", "offsets", "perm", "inv_perm", "logits")}
+    idx, _ = check_routing(cfg, gpu, x, w)
+    gate = O.gate_weights(O.router_logits(x.reshape(N, -1), w["w_router"], w.get("b_router")), idx, cfg.gate_mode)
+    ref = O.ffn_moe_forward(x.reshape(N, -1), fw["w_gate_up"], fw["w_down"], idx, gate,
+                            fw["norm_w"] if pre_norm else None, BLOCK_EPS, skip=add_skip)
+    err = rel_err(to_np(out).reshape(N, -1), ref)
+    print(f"[ffn {cfg.name} d_ff={d_ff} norm={pre_norm} skip={add_skip}] out={err:.2e} "
+          f"max|ref|={np.max(np.abs(ref)):.3g}", flush=True)
+    assert err <= TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("kw,d_ff,pre_norm,add_skip,via_forward", [
+    (dict(), 512, False, False, False),
+    (dict(), 512, True, True, True),
+    (dict(dtype="fp32"), 272, True, True, False),
+    (dict(dtype="fp32", top_k=2, gate_mode=1), 256, False, True, True),
+    (dict(top_k=2, gate_mode=1), 400, True, True, False),
+    (dict(top_k=3, gate_mode=0, n_experts=16, cfg_id=71), 512, True, False, False),
+    (dict(n_experts=1), 1024, True, True, False),
+    (dict(batch=3, seq_len=1), 512, True, True, True),
+    (dict(batch=1, seq_len=1500, d_model=264, cfg_id=72), 528, True, True, False),
+])
+def test_ffn_moe_small(kw, d_ff, pre_norm, add_skip, via_forward):
+    _ffn_case(small_cfg(weight_std=0.08, **kw), d_ff, pre_norm, add_skip, via_forward)
+
+
+@pytest.mark.parametrize("name,over,d_ff", [("cfg1", {}, 2048), ("cfg3", dict(batch=1, seq_len=4096), 4096)])
+def test_ffn_moe_big_tile_kernels(name, over, d_ff):
+    _ffn_case(get_config(name, **over), d_ff, True, True, True)
