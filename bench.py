@@ -160,6 +160,39 @@ def stack_rate(cfg, n_layers, steps, warmup):
             "output_finite": finite}
 
 
+def ffn_moe_rate(cfg, d_ff, steps, warmup):
+    """The FFN-MoE layer that follows a RoM layer and reuses its routing decision (appendix Eq. (14),
+    (15)): pre-norm, SwiGLU experts of width d_ff, skip; on the grouping rom_route leaves behind."""
+    import torch
+    from paper_2506_18145_amd import RomFfnMoe, RomLayer
+    from rom_synth import make_input, make_weights
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(4242)
+    t = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    E, Dm = cfg.n_experts, cfg.d_model
+    normal = lambda shape: (torch.randn(shape, generator=g, device="cuda:0") * cfg.weight_std).to(t)
+    layer = RomLayer(cfg, make_weights(cfg), device="cuda:0")
+    ffn = RomFfnMoe(layer, d_ff, {"w_gate_up": normal((E, 2 * d_ff, Dm)), "w_down": normal((E, Dm, d_ff)),
+                                  "norm_w": torch.ones(Dm, device="cuda:0")})
+    x = layer.to_device(make_input(cfg)).view(-1, Dm)
+    routing = layer.route(x)
+    out = torch.empty_like(x)
+    for _ in range(warmup):
+        ffn.forward(x, routing, pre_norm=True, add_skip=True, out=out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        ffn.forward(x, routing, pre_norm=True, add_skip=True, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    n_tok = x.shape[0]
+    flops = 6.0 * n_tok * cfg.top_k * Dm * d_ff
+    return {"workload": f"{cfg.name}'s tokens and routing, SwiGLU experts d_ff={d_ff}, pre-norm + skip",
+            "ms_per_call": ms, "tokens_per_s": n_tok / (ms * 1e-3), "bound": "mfma",
+            "achieved_tflops": flops / (ms * 1e-3) / 1e12, "frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+
+
 def time_forward(cfg, steps, warmup, calibrate_copy=False):
     """K timed calls of rom_layer_forward on resident inputs.  Returns (ms per call, ms per call
     without the stage events, per-stage dict)."""
@@ -255,6 +288,7 @@ def main():
                     help="skip the extra rom_step measurement (256 sequences x 512 steps, cfg4)")
     ap.add_argument("--no-shared-xdt", action="store_true",
                     help="skip the extra measurement of the shared x/dt variant of the workload")
+    ap.add_argument("--no-ffn", action="store_true", help="skip the extra FFN-MoE layer measurement")
     ap.add_argument("--stack-layers", type=int, default=48,
                     help="layers of the extra whole-stack measurement (0 = skip it)")
     ap.add_argument("--only-step", action="store_true",
@@ -311,6 +345,8 @@ def main():
             "workload": f"{cfg.name} with one shared x/dt projection (E_x = 1)", "ms_per_step": ms_s,
             "tokens_per_s": n_tok / (ms_s * 1e-3),
             "stages_ms": {k: v["ms"] for k, v in stages_s.items()}}
+    if not args.no_ffn:
+        result["ffn_moe"] = ffn_moe_rate(cfg, 2 * cfg.d_model, 20, 20)
     if args.stack_layers > 0:
         result["stack_forward"] = stack_rate(cfg, args.stack_layers, 3, 1)
     if not args.no_step:

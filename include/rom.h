@@ -237,10 +237,10 @@ ROM_API int rom_stack_step(const rom_dims *dims, const rom_block *blocks, int n_
  *   y[n, :] = sum_k gate[n, k] * f_{e(n,k)}(x[n, :]),   f_i(v) = W_down,i (SiLU(W_gate,i v) * (W_up,i v))
  * It has no router: the expert of every (token, k) slot and its weight come from the preceding
  * rom_route / rom_layer_forward / rom_block_forward call over the same N tokens, as the grouping
- * that call produced.  Optionally the experts see RMSNorm(x) (pre_norm; the norm's scale must
- * then be folded into w_gate_up with rom_ffn_fold_norm) and x is added to the result (add_skip). */
+ * that call produced.  Optionally the experts see RMSNorm(x) (pre_norm; the norm's scale is
+ * folded into the packed weight) and x is added to the result (add_skip). */
 typedef struct rom_ffn_weights {
-  const void *w_gate_up;  /* T [E, 2*d_ff, d_model]; rows [0, d_ff) gate, rows [d_ff, 2*d_ff) up */
+  const void *w_gate_up;  /* T [E, 2*d_ff, d_model] in the PACKED row order of rom_ffn_pack_gate_up */
   const void *w_down;     /* T [E, d_model, d_ff]                                              */
 } rom_ffn_weights;
 
@@ -249,15 +249,23 @@ typedef struct rom_ffn_weights {
  * matter, but dims must be a valid layer shape. */
 ROM_API size_t rom_ffn_workspace_bytes(const rom_dims *dims, int32_t d_ff, int64_t N);
 
-/* w_gate_up_folded[e, o, d] = w_gate_up[e, o, d] * norm_weight[d] (device; may be in place). */
-ROM_API int rom_ffn_fold_norm(const rom_dims *dims, int32_t d_ff, const void *w_gate_up,
-                      const float *norm_weight, void *w_gate_up_folded, void *hip_stream);
+/* Weight preparation, once per weight load.  w_gate_up is the plain layout, T [E, 2*d_ff, d_model]
+ * with rows [0, d_ff) the gate projection and rows [d_ff, 2*d_ff) the up projection.  The packed
+ * layout interleaves them in blocks of eight features,
+ *   w_packed[e, 16*b + t, :]     = w_gate_up[e, 8*b + t, :]         (gate feature 8b+t, t < 8)
+ *   w_packed[e, 16*b + 8 + t, :] = w_gate_up[e, d_ff + 8*b + t, :]  (up feature 8b+t),
+ * so that the projection kernel finds a feature's gate and up pre-activations in one lane's
+ * accumulators and can apply SiLU(gate) * up before it writes anything.  norm_weight (f32
+ * [d_model], device) != NULL multiplies every row's columns by the pre-norm's scale (use that
+ * weight with pre_norm != 0 only); NULL packs without scaling.  Not in place. */
+ROM_API int rom_ffn_pack_gate_up(const rom_dims *dims, int32_t d_ff, const void *w_gate_up,
+                         const float *norm_weight, void *w_packed, void *hip_stream);
 
 /*   x        T   [N, d_model];  out  T [N, d_model], must not alias x
  *   offsets  i32 [E+1], perm i32 [N*K], inv_perm i32 [N*K], gate f32 [N, K]: as written by
  *            rom_route, or the workspace regions of the same names after a layer / block call
  *            (that workspace must stay untouched until this call has run)
- *   pre_norm != 0: experts see x / sqrt(mean(x^2) + eps) * norm_weight (scale folded, see above)
+ *   pre_norm != 0: experts see x / sqrt(mean(x^2) + eps) * norm_weight (scale packed into the weight)
  *   add_skip != 0: out = x + y
  *   ws       rom_ffn_workspace_bytes(dims, d_ff, N) bytes, 256-byte aligned, distinct from the
  *            workspace that holds offsets / perm / inv_perm / gate

@@ -13,7 +13,7 @@ from .binding import (  # noqa: F401
     rom_balance_stats,
     rom_block_forward,
     rom_block_step,
-    rom_ffn_fold_norm,
+    rom_ffn_pack_gate_up,
     rom_ffn_moe_forward,
     rom_ffn_workspace_bytes,
     rom_fold_norm,

@@ -86,8 +86,8 @@ def load_library() -> ctypes.CDLL:
                                    I64, P, P, P, P, P, SZ, P]
     lib.rom_ffn_workspace_bytes.restype = SZ
     lib.rom_ffn_workspace_bytes.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, I64]
-    lib.rom_ffn_fold_norm.restype = ctypes.c_int
-    lib.rom_ffn_fold_norm.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, P, P, P, P]
+    lib.rom_ffn_pack_gate_up.restype = ctypes.c_int
+    lib.rom_ffn_pack_gate_up.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, P, P, P, P]
     lib.rom_ffn_moe_forward.restype = ctypes.c_int
     lib.rom_ffn_moe_forward.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, ctypes.POINTER(_RomFfnWeights),
                                         ctypes.c_int, F32, ctypes.c_int, P, I64, P, P, P, P, P, P, SZ, P]
@@ -227,9 +227,9 @@ def rom_ffn_workspace_bytes(dims, d_ff: int, n_tokens: int) -> int:
     return int(load_library().rom_ffn_workspace_bytes(ctypes.byref(dims), d_ff, n_tokens))
 
 
-def rom_ffn_fold_norm(dims, d_ff, w_gate_up, norm_weight, w_gate_up_folded):
-    _check(load_library().rom_ffn_fold_norm(ctypes.byref(dims), d_ff, _ptr(w_gate_up), _ptr(norm_weight),
-                                            _ptr(w_gate_up_folded), _stream()), "rom_ffn_fold_norm")
+def rom_ffn_pack_gate_up(dims, d_ff, w_gate_up, norm_weight, w_packed):
+    _check(load_library().rom_ffn_pack_gate_up(ctypes.byref(dims), d_ff, _ptr(w_gate_up), _ptr(norm_weight),
+                                               _ptr(w_packed), _stream()), "rom_ffn_pack_gate_up")
 
 
 def rom_ffn_moe_forward(dims, d_ff, w_gate_up, w_down, pre_norm, eps, add_skip, x, n_tokens, offsets, perm,
@@ -460,14 +460,19 @@ class RomFfnMoe:
         self.w_gate_up = conv(weights["w_gate_up"], layer.tdtype)
         self.w_down = conv(weights["w_down"], layer.tdtype)
         self.norm_w = conv(weights["norm_w"], torch.float32) if weights.get("norm_w") is not None else None
-        self._folded: Optional[torch.Tensor] = None
+        self._packed: Dict[bool, torch.Tensor] = {}
         self._ws: Optional[torch.Tensor] = None
 
-    def folded(self) -> torch.Tensor:
-        if self._folded is None:
-            self._folded = torch.empty_like(self.w_gate_up)
-            rom_ffn_fold_norm(self.dims, self.d_ff, self.w_gate_up, self.norm_w, self._folded)
-        return self._folded
+    def packed(self, pre_norm: bool, drop_plain: bool = False) -> torch.Tensor:
+        """w_gate_up in the library's packed row order, with the pre-norm's scale folded in or not."""
+        if pre_norm not in self._packed:
+            out = torch.empty_like(self.w_gate_up)
+            rom_ffn_pack_gate_up(self.dims, self.d_ff, self.w_gate_up, self.norm_w if pre_norm else None, out)
+            self._packed[pre_norm] = out
+            if drop_plain:
+                torch.cuda.synchronize()
+                self.w_gate_up = None
+        return self._packed[pre_norm]
 
     def forward(self, x: torch.Tensor, routing, pre_norm: bool = False, add_skip: bool = False,
                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
@@ -480,7 +485,7 @@ class RomFfnMoe:
             self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         if out is None:
             out = torch.empty_like(x)
-        rom_ffn_moe_forward(self.dims, self.d_ff, self.folded() if pre_norm else self.w_gate_up, self.w_down,
+        rom_ffn_moe_forward(self.dims, self.d_ff, self.packed(bool(pre_norm)), self.w_down,
                             pre_norm, self.eps, add_skip, x, n, routing["offsets"], routing["perm"],
                             routing["inv_perm"], routing["gate"], out, self._ws)
         return out

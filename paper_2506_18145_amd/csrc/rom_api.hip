@@ -251,6 +251,22 @@ __global__ void fold_cols_kernel(const T *src, const float *__restrict__ scale, 
   dst[i] = from_f32<T>(to_f32(src[i]) * scale[i % n_cols]);
 }
 
+// dst[e, 16b + t, d] = src[e, 8b + t, d] * scale[d], dst[e, 16b + 8 + t, d] = src[e, d_ff + 8b + t, d] * scale[d]
+// (t < 8; scale may be NULL): gate and up rows of a SwiGLU expert interleaved in blocks of eight
+template <typename T>
+__global__ void pack_gate_up_kernel(const T *__restrict__ src, const float *__restrict__ scale, T *__restrict__ dst,
+                                    int n_experts, int d_ff, int d_model) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t per_expert = static_cast<int64_t>(2) * d_ff * d_model;
+  if (i >= n_experts * per_expert) return;
+  const int64_t e = i / per_expert, rem = i % per_expert;
+  const int r = static_cast<int>(rem / d_model), d = static_cast<int>(rem % d_model);
+  const int b = r / 16, t = r % 16;
+  const int src_row = t < 8 ? 8 * b + t : d_ff + 8 * b + (t - 8);
+  const float v = to_f32(src[e * per_expert + static_cast<int64_t>(src_row) * d_model + d]);
+  dst[i] = from_f32<T>(scale ? v * scale[d] : v);
+}
+
 struct SegTok {
   int64_t t[kMaxSegments + 1];
 };
@@ -554,7 +570,11 @@ FfnPlan make_ffn_plan(const rom_dims *d, int32_t d_ff, int64_t n_tok) {
   const size_t S = static_cast<size_t>(n_tok) * d->top_k, b = d->dtype == ROM_DTYPE_BF16 ? 2 : 4;
   p.tok_of_pos = take(S * 4);
   p.rstd = take(S * 4);
-  p.h = take(S * 2 * d_ff * b);
+  // gate | up pre-activations: only the plain FMA kernel (fp32, or operands beyond the MFMA
+  // kernels' 32-bit element offsets) writes them out; the MFMA kernels apply SwiGLU themselves
+  const bool fused = d->dtype == ROM_DTYPE_BF16 && static_cast<int64_t>(n_tok) * d->d_model < (1ll << 32) &&
+                     static_cast<int64_t>(2) * d_ff * d->d_model < (1ll << 32);
+  p.h = fused ? kNone : take(S * 2 * d_ff * b);
   p.a = take(S * d_ff * b);
   p.op_sorted = d->top_k > 1 ? take(S * d->d_model * b) : kNone;
   p.total = off;
@@ -714,21 +734,20 @@ size_t rom_ffn_workspace_bytes(const rom_dims *dims, int32_t d_ff, int64_t N) {
   return make_ffn_plan(dims, d_ff, N > 0 ? N : 1).total;
 }
 
-int rom_ffn_fold_norm(const rom_dims *dims, int32_t d_ff, const void *w_gate_up, const float *norm_weight,
-                      void *w_gate_up_folded, void *hip_stream) {
+int rom_ffn_pack_gate_up(const rom_dims *dims, int32_t d_ff, const void *w_gate_up, const float *norm_weight,
+                         void *w_packed, void *hip_stream) {
   int rc = check_ffn(dims, d_ff);
   if (rc != ROM_OK) return rc;
-  if (!w_gate_up || !norm_weight || !w_gate_up_folded) return ROM_E_INVAL;
-  const int64_t rows = static_cast<int64_t>(dims->n_experts) * 2 * d_ff;
-  const int64_t n = rows * dims->d_model;
+  if (!w_gate_up || !w_packed || w_gate_up == w_packed) return ROM_E_INVAL;
+  const int64_t n = static_cast<int64_t>(dims->n_experts) * 2 * d_ff * dims->d_model;
   const dim3 grid(static_cast<unsigned>(ceil_div(n, 256)));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (dims->dtype == ROM_DTYPE_BF16)
-    hipLaunchKernelGGL(fold_cols_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(w_gate_up),
-                       norm_weight, static_cast<bf16_t *>(w_gate_up_folded), rows, dims->d_model);
+    hipLaunchKernelGGL(pack_gate_up_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(w_gate_up),
+                       norm_weight, static_cast<bf16_t *>(w_packed), dims->n_experts, d_ff, dims->d_model);
   else
-    hipLaunchKernelGGL(fold_cols_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(w_gate_up),
-                       norm_weight, static_cast<float *>(w_gate_up_folded), rows, dims->d_model);
+    hipLaunchKernelGGL(pack_gate_up_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(w_gate_up),
+                       norm_weight, static_cast<float *>(w_packed), dims->n_experts, d_ff, dims->d_model);
   return hipGetLastError() == hipSuccess ? ROM_OK : ROM_E_HIP;
 }
 
@@ -761,10 +780,16 @@ int rom_ffn_moe_forward(const rom_dims *dims, int32_t d_ff, const rom_ffn_weight
   ga.A = x; ga.lda = Dm; ga.a_rows = tok_of_pos; ga.a_span = N * Dm;
   ga.W = w->w_gate_up; ga.N = 2 * d_ff; ga.K = Dm;
   ga.offsets = offsets; ga.n_groups = E; ga.M = S;
-  ga.C = base + p.h; ga.ldc = 2 * d_ff;
   ga.row_scale = rstd;                      // pre-norm: the weight's columns carry the norm's scale
-  ROM_TRY(launch_grouped_gemm(ga, s));
-  ROM_TRY(launch_swiglu(dims->dtype, base + p.h, base + p.a, S, d_ff, s));
+  ga.C = base + p.a; ga.ldc = d_ff; ga.swiglu = 1;
+  if (grouped_gemm_on_mfma(ga)) {           // SiLU(gate) * up formed in the GEMM's epilogue
+    ROM_TRY(launch_grouped_gemm(ga, s));
+  } else {
+    if (p.h == kNone) return ROM_E_UNSUPPORTED;   // cannot happen for 16-byte aligned, in-range operands
+    ga.C = base + p.h; ga.ldc = 2 * d_ff; ga.swiglu = 0;
+    ROM_TRY(launch_grouped_gemm(ga, s));
+    ROM_TRY(launch_swiglu(dims->dtype, base + p.h, base + p.a, S, d_ff, s));
+  }
 
   // down projection, weighted by the router's R_i and brought back to token order
   memset(&ga, 0, sizeof(ga));

@@ -93,7 +93,8 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmArgs &a, int BM, int 
 }
 
 // epilogue variants of the MFMA kernel (compile-time, so the store loop has no branches)
-enum { kEpiPlain = 0, kEpiBiasSoftplus = 1, kEpiRowScale = 2, kEpiPlainF32 = 3, kEpiRowScaleResidual = 4 };
+enum { kEpiPlain = 0, kEpiBiasSoftplus = 1, kEpiRowScale = 2, kEpiPlainF32 = 3, kEpiRowScaleResidual = 4,
+       kEpiSwiGLU = 5 };
 
 __device__ __forceinline__ void store_out(const GemmArgs &a, int64_t crow, int col, float v) {
   if (a.bias) v += a.bias[col];
@@ -140,6 +141,52 @@ __device__ __forceinline__ void mfma_epilogue(const GemmArgs &a, const TileCoord
             *reinterpret_cast<float4 *>(static_cast<float *>(a.C) + blockIdx.y * a.c_split_stride +
                                         crow * a.ldc + col) =
                 make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        }
+      }
+    }
+  } else if constexpr (EPI == kEpiSwiGLU) {
+    // The weight's rows come in blocks of 16: gate features 8b..8b+7, then up features 8b..8b+7.
+    // A lane's accumulator elements 8m..8m+3 and 8m+4..8m+7 of a 32-wide tile are then the gate
+    // and the up pre-activation of the same four features of the same row, so
+    // SiLU(gate) * up is formed in registers and the output tile is half as wide as the product.
+    constexpr int kOutW = WTN / 2;
+    constexpr int kPitch = kOutW * 2 + 16;
+    char *stage = reinterpret_cast<char *>(smem) + wave * (32 * kPitch);
+    constexpr int kChunks = kOutW / 8;
+    constexpr int kRowsPerPass = 64 / kChunks;
+    const int chunk = lane % kChunks, sub = lane / kChunks;
+    const int col = (tc.n0 + wn * WTN) / 2 + chunk * 8;
+    const int n_out = a.N / 2;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      float scale = 1.0f;
+      if (a.row_scale) {                   // pre-norm: 1 / rms of the row, before the activation
+        const int64_t p = tc.row0 + wm * WTM + i * 32 + frag_row;
+        scale = p < tc.row_end ? a.row_scale[a.c_rows ? a.c_rows[p] : p] : 0.0f;
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+          float o[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            o[r] = silu_f32(acc[i][j][8 * m + r] * scale) * (acc[i][j][8 * m + 4 + r] * scale);
+          uint2 pk;
+          pk.x = pack_bf16x2(o[0], o[1]);
+          pk.y = pack_bf16x2(o[2], o[3]);
+          const int lcol = (j * 2 + m) * 8 + frag_half * 4;
+          *reinterpret_cast<uint2 *>(stage + frag_row * kPitch + lcol * 2) = pk;
+        }
+      }
+#pragma unroll 4
+      for (int r0 = 0; r0 < 32; r0 += kRowsPerPass) {
+        const int row = r0 + sub;
+        const int64_t p = tc.row0 + wm * WTM + i * 32 + row;
+        if (row < 32 && p < tc.row_end && col < n_out) {
+          const int64_t crow = a.c_rows ? a.c_rows[p] : p;
+          const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * kPitch + chunk * 16);
+          *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.C) + crow * a.ldc + col) = v;
         }
       }
     }
@@ -875,21 +922,29 @@ hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
 
 }  // namespace
 
+// whether the call takes the MFMA kernels (else the plain FMA kernel, which has no fused SwiGLU)
+bool grouped_gemm_on_mfma(const GemmArgs &a) {
+  const int out_align = a.c_is_f32 ? 4 : 8;      // elements per output store
+  return a.dtype == ROM_DTYPE_BF16 && a.K % 8 == 0 && a.lda % 8 == 0 &&
+         a.N % out_align == 0 && a.ldc % out_align == 0 && (reinterpret_cast<uintptr_t>(a.A) % 16 == 0) &&
+         (reinterpret_cast<uintptr_t>(a.W) % 16 == 0) &&
+         (reinterpret_cast<uintptr_t>(a.C) % 16 == 0) && a.a_span < (1ll << 32) &&
+         static_cast<int64_t>(a.N) * a.K < (1ll << 32) &&
+         !(a.bias && !a.softplus) && !(a.softplus && !a.bias) &&
+         !(a.row_scale && (a.bias || a.c_is_f32)) && !(a.bias && a.c_is_f32) &&
+         !(a.residual && !a.row_scale) && (reinterpret_cast<uintptr_t>(a.residual) % 16 == 0) &&
+         !(a.swiglu && (a.bias || a.c_is_f32 || a.residual || a.N % 16 != 0));
+}
+
 hipError_t launch_grouped_gemm(const GemmArgs &args, hipStream_t s) {
   if (args.M <= 0) return hipSuccess;
   GemmArgs a = args;
   if (a.k_splits < 1 || !a.c_is_f32 || a.bias || a.row_scale || a.residual) a.k_splits = 1;   // partial sums need a plain fp32 output
   a.k_per_split = static_cast<int>(ceil_div(ceil_div(a.K, a.k_splits), 64) * 64);
   a.k_splits = static_cast<int>(ceil_div(a.K, a.k_per_split));
-  const int out_align = a.c_is_f32 ? 4 : 8;      // elements per output store
-  const bool mfma_ok = a.dtype == ROM_DTYPE_BF16 && a.K % 8 == 0 && a.lda % 8 == 0 &&
-                       a.N % out_align == 0 && a.ldc % out_align == 0 && (reinterpret_cast<uintptr_t>(a.A) % 16 == 0) &&
-                       (reinterpret_cast<uintptr_t>(a.W) % 16 == 0) &&
-                       (reinterpret_cast<uintptr_t>(a.C) % 16 == 0) && a.a_span < (1ll << 32) &&
-                       static_cast<int64_t>(a.N) * a.K < (1ll << 32) &&
-                       !(a.bias && !a.softplus) && !(a.softplus && !a.bias) &&
-                       !(a.row_scale && (a.bias || a.c_is_f32)) && !(a.bias && a.c_is_f32) &&
-                       !(a.residual && !a.row_scale) && (reinterpret_cast<uintptr_t>(a.residual) % 16 == 0);
+  const bool mfma_ok = grouped_gemm_on_mfma(a);
+  if (a.swiglu && !mfma_ok) return hipErrorInvalidValue;      // the caller asks grouped_gemm_on_mfma first
+  if (a.swiglu) return launch_mfma_tiles<kEpiSwiGLU>(a, s);
   if (!mfma_ok) {
     const dim3 grid(grid_tiles(a, kSB, kSB), a.k_splits);
     if (a.dtype == ROM_DTYPE_BF16)

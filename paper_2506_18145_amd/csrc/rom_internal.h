@@ -79,12 +79,15 @@ struct GemmArgs {
   int softplus;              // apply softplus after bias
   const float *row_scale;    // indexed by c_row (NULL = 1): multiplies the row
   const void *residual;      // type T, laid out like C (row c_row, pitch ldc), or NULL: added after the row scale
+  int swiglu;                // 1: W's rows are blocks of 8 gate + 8 up features; C [*, N/2] = SiLU(gate) * up
+                             // (after the row scale); MFMA kernels only, see grouped_gemm_on_mfma
   int k_splits;              // > 1: slice the inner dimension; slice s writes its partial sums (fp32, plain
                              // epilogue only) to C + s * c_split_stride; the consumer adds the slices up
   int64_t c_split_stride;    // elements between the outputs of consecutive slices
   int k_per_split;           // filled in by launch_grouped_gemm
 };
 hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s);
+bool grouped_gemm_on_mfma(const GemmArgs &a);
 
 // ---------------------------------------------------------------- sequence kernels
 // sum over the K slots of a token: dst[n, :] = act(row_scale[n] * sum_k src[inv_perm[n*K+k], :] + bias)
@@ -114,7 +117,8 @@ hipError_t launch_combine(int dtype, const void *op, const int32_t *inv_perm, co
                           hipStream_t s);
 
 // ---------------------------------------------------------------- FFN-MoE (Eq. (14), (15))
-// a[p, :] = SiLU(h[p, :d_ff]) * h[p, d_ff:]   (h T [n_rows, 2*d_ff], a T [n_rows, d_ff]; d_ff % 8 == 0)
+// a[p, 8b + t] = SiLU(h[p, 16b + t]) * h[p, 16b + 8 + t], t < 8: h's columns are blocks of 8 gate + 8 up
+// features (h T [n_rows, 2*d_ff], a T [n_rows, d_ff]; d_ff % 8 == 0)
 hipError_t launch_swiglu(int dtype, const void *h, void *a, int64_t n_rows, int d_ff, hipStream_t s);
 // tok_of_pos[p] = perm[p] / K; rstd_sorted (may be NULL) [p] = 1 / sqrt(mean(x[tok_of_pos[p]]^2) + eps)
 hipError_t launch_ffn_prep(int dtype, const int32_t *perm, int top_k, int64_t n_slots, const void *x,

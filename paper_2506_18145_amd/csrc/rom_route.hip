@@ -395,23 +395,35 @@ __global__ __launch_bounds__(kBalanceBlock) void balance_partial_kernel(
   }
 }
 
-__global__ __launch_bounds__(kWave) void balance_finish_kernel(
+// One block of kFinishWaves wavefronts, lane = expert: wave w adds the block sums b = w, w + 16, ...
+// in that order, wave 0 then adds the 16 wave sums in wave order - a fixed tree, so the result
+// does not depend on timing, and no lane walks more than 16 dependent loads.
+constexpr int kFinishWaves = 16;
+__global__ __launch_bounds__(kFinishWaves * kWave) void balance_finish_kernel(
     const float *__restrict__ partial, int n_blocks, const int32_t *__restrict__ counts,
     int64_t n_tokens, int n_experts, int top_k, float alpha, float *__restrict__ frac,
     float *__restrict__ mean_prob, float *__restrict__ loss) {
-  const int e = threadIdx.x;
+  __shared__ float wave_part[kFinishWaves][kWave];
+  const int e = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  float t = 0.0f;
+  if (e < n_experts)
+    for (int b = wave; b < n_blocks; b += kFinishWaves) t += partial[static_cast<int64_t>(b) * n_experts + e];
+  wave_part[wave][e] = t;
+  __syncthreads();
+  if (wave != 0) return;
   float prod = 0.0f;
   if (e < n_experts) {
-    float t = 0.0f;
-    for (int b = 0; b < n_blocks; ++b) t += partial[static_cast<int64_t>(b) * n_experts + e];
-    const float pm = t / static_cast<float>(n_tokens);
+    float total = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kFinishWaves; ++w) total += wave_part[w][e];
+    const float pm = total / static_cast<float>(n_tokens);
     const float f = static_cast<float>(counts[e]) / (static_cast<float>(n_tokens) * static_cast<float>(top_k));
     frac[e] = f;
     mean_prob[e] = pm;
     prod = f * pm;
   }
-  const float total = wave_sum(prod);
-  if (e == 0) *loss = alpha * static_cast<float>(n_experts) * total;
+  const float sum = wave_sum(prod);
+  if (e == 0) *loss = alpha * static_cast<float>(n_experts) * sum;
 }
 
 template <typename T, bool NORM>
@@ -475,7 +487,7 @@ hipError_t launch_balance_stats(const float *logits, const int32_t *counts, int6
   if (blocks > kBalanceMaxBlocks) blocks = kBalanceMaxBlocks;
   hipLaunchKernelGGL(balance_partial_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBalanceBlock), 0,
                      s, logits, n_tokens, n_experts, ep, partial);
-  hipLaunchKernelGGL(balance_finish_kernel, dim3(1), dim3(kWave), 0, s, partial, static_cast<int>(blocks),
+  hipLaunchKernelGGL(balance_finish_kernel, dim3(1), dim3(kFinishWaves * kWave), 0, s, partial, static_cast<int>(blocks),
                      counts, n_tokens, n_experts, top_k, alpha, frac, mean_prob, loss);
   return hipGetLastError();
 }

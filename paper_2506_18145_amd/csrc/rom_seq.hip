@@ -650,7 +650,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const T *__restrict__ op,
 }
 
 // ------------------------------------------------------------------ FFN-MoE helpers, Eq. (14), (15)
-// a[p, f] = SiLU(h[p, f]) * h[p, d_ff + f]: the SwiGLU of one expert's gate | up projection row
+// a[p, 8b + t] = SiLU(h[p, 16b + t]) * h[p, 16b + 8 + t]: the SwiGLU of one expert's projection row,
+// whose columns come in blocks of 8 gate + 8 up features (the packed weight's row order)
 template <typename T>
 __global__ __launch_bounds__(256) void swiglu_kernel(const T *__restrict__ h, T *__restrict__ a,
                                                      int64_t n_rows, int d_ff) {
@@ -661,8 +662,9 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const T *__restrict__ h, T 
   const int64_t row = idx / groups;
   const int c0 = static_cast<int>(idx % groups) * V;
   Chunk<T> g, u, o;
-  g.load(h + row * 2 * d_ff + c0);
-  u.load(h + row * 2 * d_ff + d_ff + c0);
+  const int goff = 16 * (c0 / 8) + (c0 % 8);
+  g.load(h + row * 2 * d_ff + goff);
+  u.load(h + row * 2 * d_ff + goff + 8);
 #pragma unroll
   for (int i = 0; i < V / 2; ++i)
     o.set_pair(i, silu_f32(g.get(2 * i)) * u.get(2 * i), silu_f32(g.get(2 * i + 1)) * u.get(2 * i + 1));

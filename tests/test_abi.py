@@ -236,4 +236,5 @@ def test_ffn_moe_arguments_and_workspace(lib):
     assert call(d, 32, ctypes.byref(w), addr, addr + 4096, 8, addr, 4096) == -2       # workspace too small
     assert lib.rom_ffn_moe_forward(ctypes.byref(d), 32, ctypes.byref(w), 1, F(-1.0), 1, addr, 8, addr, addr, addr,
                                    addr, addr + 4096, addr, 4096, None) == -1         # negative eps
-    assert lib.rom_ffn_fold_norm(ctypes.byref(d), 32, None, addr, addr, None) == -1
+    assert lib.rom_ffn_pack_gate_up(ctypes.byref(d), 32, None, addr, addr + 4096, None) == -1
+    assert lib.rom_ffn_pack_gate_up(ctypes.byref(d), 32, addr, None, addr, None) == -1     # not in place
