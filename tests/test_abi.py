@@ -80,6 +80,23 @@ def test_invalid_dims_are_rejected_before_any_launch(lib):
                                  0, None) == -1
 
 
+def test_sizes_beyond_the_supported_range_are_refused(lib):
+    """More than 65535 sequences, or more than 2^30 (token, k) slots: ROM_E_UNSUPPORTED before the
+    workspace is even looked at."""
+    from paper_2506_18145_amd import binding
+    d = _dims(top_k=2)
+    buf = ctypes.create_string_buffer(4096 + 256)
+    addr = (ctypes.addressof(buf) + 255) // 256 * 256
+    w = binding._RomWeights(*([addr] * 11))
+    fwd = lambda B, L: lib.rom_layer_forward(ctypes.byref(d), ctypes.byref(w), addr, B, L, None, None,
+                                             addr + 2048, None, None, addr, 4096, None)
+    assert fwd(65536, 1) == -3
+    assert fwd(1, (1 << 29) + 1) == -3
+    assert fwd(65535, 1) == -2 and fwd(1, 1 << 20) == -2      # in range: only the workspace is too small
+    assert lib.rom_route(ctypes.byref(d), ctypes.byref(w), addr, (1 << 29) + 1, addr, addr, addr, addr, addr,
+                         addr, None, addr, 4096, None) == -3
+
+
 def test_error_strings_and_stage_names(lib):
     assert lib.rom_strerror(0) == b"ok"
     for code in (-1, -2, -3, -4):

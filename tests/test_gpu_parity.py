@@ -245,6 +245,24 @@ def test_full_size_configs(name):
     compare_layer(cfg, gpu, x, w)
 
 
+@pytest.mark.parametrize("kw", [
+    # one very long sequence, the most experts and the largest K the library takes
+    dict(batch=1, seq_len=200_000, d_model=64, d_inner=64, dt_rank=4, n_experts=64, top_k=8, gate_mode=1,
+         cfg_id=90),
+    # the largest number of sequences a call takes, one token each (the step path's grids)
+    dict(batch=65535, seq_len=1, d_model=64, d_inner=64, dt_rank=4, n_experts=4, top_k=1, cfg_id=91),
+    # many short sequences: the batch dimension of the conv / scan grids, fp32
+    dict(batch=4099, seq_len=5, d_model=64, d_inner=32, dt_rank=4, n_experts=3, top_k=2, dtype="fp32", cfg_id=92),
+])
+def test_size_limits(kw):
+    """The extremes of the supported range (sequence length, batch, experts, K) at narrow
+    widths, every element against the oracle."""
+    cfg = small_cfg(**kw)
+    cs, ss = make_states(cfg)
+    _, gpu, x, w = run_layer(cfg, cs, ss)
+    compare_layer(cfg, gpu, x, w, cs, ss)
+
+
 def _step_run(cfg, n_steps, tracked, all_steps):
     """Runs n_steps of rom_step on all sequences; the oracle follows `tracked` sequences through
     every step and all sequences through the first `all_steps` steps."""
