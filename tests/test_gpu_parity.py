@@ -183,6 +183,50 @@ def test_random_shapes(seed):
         compare_layer(cfg, gpu, x, w, cs, ss)
 
 
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_shapes_block_and_ffn(seed):
+    """The same kind of random shapes through the pre-norm residual block, then an FFN-MoE layer of
+    random width on the grouping the block call left in its workspace."""
+    import random
+    from paper_2506_18145_amd import rom_set_segments
+    from rom_synth import round_to_bf16
+    rng = random.Random(seed)
+    for i in range(8):
+        E = rng.choice([1, 2, 3, 5, 8, 12, 16, 33, 64])
+        kw = dict(name=f"random-block-{seed}-{i}", cfg_id=800 + 20 * seed + i, batch=rng.choice([1, 1, 2, 3, 5]),
+                  seq_len=rng.choice([1, 2, 7, 31, 64, 65, 130, 257, 700, 1500]),
+                  d_model=8 * rng.randint(4, 80), d_inner=16 * rng.randint(2, 70), d_state=16, d_conv=4,
+                  dt_rank=rng.choice([1, 3, 8, 16, 24, 32, 48, 64, 128]), n_experts=E,
+                  top_k=rng.randint(1, min(E, 4)), dtype=rng.choice(["bf16", "bf16", "fp32"]),
+                  gate_mode=rng.choice([0, 1]), routed_xdt=rng.choice([True, True, False]), weight_std=0.06)
+        cfg = RomConfig(**kw)
+        seg = rng.choice([0, 0, 2, 3])
+        cs, ss = make_states(cfg) if rng.choice([False, True]) else (None, None)
+        d_ff = 16 * rng.randint(1, 70)
+        pre_norm, skip = rng.choice([False, True]), rng.choice([False, True])
+        print(f"[{cfg.name}] B={cfg.batch} L={cfg.seq_len} Dm={cfg.d_model} De={cfg.d_inner} R={cfg.dt_rank} "
+              f"E={E} K={cfg.top_k} {cfg.dtype} segments={seg} d_ff={d_ff} norm={pre_norm} skip={skip}", flush=True)
+        rom_set_segments(seg)
+        try:
+            layer, gpu, x, w = run_layer(cfg, cs, ss, block=True)
+        finally:
+            rom_set_segments(0)
+        compare_layer(cfg, gpu, x, w, cs, ss, block=True)
+        B, L = cfg.batch, cfg.seq_len
+        N = B * L
+        fw = make_ffn_weights(cfg, d_ff)
+        ffn = RomFfnMoe(layer, d_ff, fw, eps=BLOCK_EPS)
+        routing = {k: layer.ws_view(k, B, L) for k in ("offsets", "perm", "inv_perm", "gate")}
+        x2 = make_input(cfg) * np.float32(0.7)
+        x2 = round_to_bf16(x2) if cfg.dtype == "bf16" else x2
+        out = ffn.forward(layer.to_device(x2), routing, pre_norm=pre_norm, add_skip=skip)
+        torch.cuda.synchronize()
+        # the block's own expert choice and weights (checked against the oracle just above)
+        ref = O.ffn_moe_forward(x2.reshape(N, -1), fw["w_gate_up"], fw["w_down"], gpu["expert_idx"], gpu["gate"],
+                                fw["norm_w"] if pre_norm else None, BLOCK_EPS, skip=skip)
+        assert rel_err(to_np(out).reshape(N, -1), ref) <= TOL[cfg.dtype]
+
+
 def test_carried_state_and_split_sequence():
     cfg = small_cfg(seq_len=150, top_k=2, gate_mode=1)
     cs, ss = make_states(cfg)
