@@ -529,3 +529,27 @@ def test_ffn_moe_small(kw, d_ff, pre_norm, add_skip, via_forward):
 @pytest.mark.parametrize("name,over,d_ff", [("cfg1", {}, 2048), ("cfg3", dict(batch=1, seq_len=4096), 4096)])
 def test_ffn_moe_big_tile_kernels(name, over, d_ff):
     _ffn_case(get_config(name, **over), d_ff, True, True, True)
+
+
+@pytest.mark.parametrize("kw", [dict(), dict(dtype="fp32"), dict(top_k=2, gate_mode=1, n_experts=8, cfg_id=73)])
+def test_rom_block_then_ffn_moe_chain(kw):
+    """The hybrid pair of the appendix end to end: a RoM block, then an FFN-MoE block that reads the
+    RoM block's output and runs on the RoM block's routing decision (no second router), against the
+    oracle's chain.  The FFN makes no decision of its own, so the two chains stay comparable."""
+    cfg = small_cfg(weight_std=0.08, batch=2, seq_len=333, **kw)
+    w, x = make_weights(cfg), make_input(cfg)
+    fw = make_ffn_weights(cfg, 768)
+    layer, gpu, x, w = run_layer(cfg, block=True)
+    ref, _ = compare_layer(cfg, gpu, x, w, block=True)
+    B, L = cfg.batch, cfg.seq_len
+    N = B * L
+    ffn = RomFfnMoe(layer, 768, fw, eps=BLOCK_EPS)
+    routing = {k: layer.ws_view(k, B, L) for k in ("offsets", "perm", "inv_perm", "gate")}
+    mid = layer.block_forward(layer.to_device(x), eps=BLOCK_EPS)
+    out = ffn.forward(mid, routing, pre_norm=True, add_skip=True)
+    torch.cuda.synchronize()
+    want = O.ffn_moe_forward(ref["out"].reshape(N, -1), fw["w_gate_up"], fw["w_down"], ref["expert_idx"],
+                             ref["gate"], fw["norm_w"], BLOCK_EPS, skip=True)
+    assert rel_err(to_np(out).reshape(N, -1), want) <= TOL[cfg.dtype]
+    # the FFN branch is not negligible next to its skip term
+    assert np.max(np.abs(want - ref["out"].reshape(N, -1))) > 0.05 * np.max(np.abs(want))
