@@ -8,6 +8,10 @@
  * joins back into the caller's stream inside the call) and never synchronises (the
  * rom_profile_* helpers excepted).  Buffers must stay valid until the stream has passed the
  * end of the call.
+ * Because of that a call with rom_set_segments < 2 and profiling off may be recorded into a
+ * HIP graph (stream capture) and replayed, once one call of the same shape has run outside a
+ * capture: the first use of a kernel that needs more than 64 KiB of LDS sets a function
+ * attribute, which is not a stream operation.
  *
  * The layer (paper Sec. 4.2, Eq. (9)-(13), on top of the Mamba layer of Sec. 3.1,
  * Eq. (1)-(6)):

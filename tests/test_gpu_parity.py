@@ -553,3 +553,41 @@ def test_rom_block_then_ffn_moe_chain(kw):
     assert rel_err(to_np(out).reshape(N, -1), want) <= TOL[cfg.dtype]
     # the FFN branch is not negligible next to its skip term
     assert np.max(np.abs(want - ref["out"].reshape(N, -1))) > 0.05 * np.max(np.abs(want))
+
+
+def test_step_and_block_step_replay_from_a_captured_graph():
+    """rom_step / rom_block_step allocate nothing, never synchronise and record no memset, so a
+    caller may capture them in a HIP graph: four replays (with the test's own eager work and
+    synchronisations between them) give bit for bit what four eager calls give."""
+    cfg = small_cfg(batch=9, seq_len=4, top_k=2, gate_mode=1, n_experts=8, cfg_id=75, weight_std=0.08)
+    w = make_weights(cfg)
+    layer = RomLayer(cfg, w)
+    xs = layer.to_device(make_input(cfg))                       # [B, 4, d_model]: four steps
+    cs0, ss0 = make_states(cfg)
+    for fn in (lambda x, c, s_, o: layer.step(x, c, s_, o),
+               lambda x, c, s_, o: layer.block_step(x, c, s_, o, eps=BLOCK_EPS)):
+        cs, ss = layer.to_device(cs0, typed=False), layer.to_device(ss0, typed=False)
+        eager = []
+        for t in range(4):
+            eager.append(fn(xs[:, t].contiguous(), cs, ss, None).clone())
+        eager_cs, eager_ss = cs.clone(), ss.clone()
+        torch.cuda.synchronize()
+        # capture one step on static buffers
+        x_static = xs[:, 0].contiguous().clone()
+        out_static = torch.empty_like(x_static)
+        cs.copy_(layer.to_device(cs0, typed=False))
+        ss.copy_(layer.to_device(ss0, typed=False))
+        fn(x_static, cs, ss, out_static)                        # warm-up outside the capture (lazy setup)
+        cs.copy_(layer.to_device(cs0, typed=False))
+        ss.copy_(layer.to_device(ss0, typed=False))
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fn(x_static, cs, ss, out_static)
+        for t in range(4):
+            x_static.copy_(xs[:, t])
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out_static, eager[t]), f"replay {t}"
+            _ = (eager[t].float() * 2).sum().item()             # eager work between the replays
+        assert torch.equal(cs, eager_cs) and torch.equal(ss, eager_ss)
