@@ -62,7 +62,7 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmArgs &a, int BM, int 
   const int patches_n = (n_tiles + pn - 1) / pn;
   const int G = gridDim.x;
   int t = blockIdx.x;
-  if (kXcdRemap && G % 8 == 0) t = (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8;
+  if (kXcdRemap && !a.no_xcd_remap && G % 8 == 0) t = (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8;
   const int patch = t / kPatchTiles, in_patch = t % kPatchTiles;
   const int mt = (patch / patches_n) * pm + in_patch % pm;
   const int nt = (patch % patches_n) * pn + in_patch / pm;
@@ -917,7 +917,13 @@ hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
     return launch_mfma<256, 256, 4, 2, EPI>(a, s);
   }
   if (rows_per_group >= 96) return launch_mfma<128, 128, 2, 2, EPI>(a, s);
-  return launch_mfma<64, 128, 2, 2, EPI>(a, s);
+  // One row tile per group at most (the recurrent step): every weight tile is read by exactly one
+  // workgroup, so there is no L2 sharing for the XCD runs to protect, while a run of logical tiles
+  // is one expert's column tiles - with few active experts the runs would put all the work on a
+  // few XCDs.  Deal the tiles round-robin instead.
+  GemmArgs spread = a;
+  spread.no_xcd_remap = 1;
+  return launch_mfma<64, 128, 2, 2, EPI>(spread, s);
 }
 
 }  // namespace

@@ -81,6 +81,7 @@ struct GemmArgs {
   const void *residual;      // type T, laid out like C (row c_row, pitch ldc), or NULL: added after the row scale
   int swiglu;                // 1: W's rows are blocks of 8 gate + 8 up features; C [*, N/2] = SiLU(gate) * up
                              // (after the row scale); MFMA kernels only, see grouped_gemm_on_mfma
+  int no_xcd_remap;          // set by the launcher: logical tile = workgroup id (no contiguous run per XCD)
   int k_splits;              // > 1: slice the inner dimension; slice s writes its partial sums (fp32, plain
                              // epilogue only) to C + s * c_split_stride; the consumer adds the slices up
   int64_t c_split_stride;    // elements between the outputs of consecutive slices
