@@ -193,6 +193,39 @@ def ffn_moe_rate(cfg, d_ff, steps, warmup):
             "achieved_tflops": flops / (ms * 1e-3) / 1e12, "frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
 
 
+def hybrid_stack_rate(cfg, n_layers, d_ff, steps, warmup):
+    """n_layers RoM blocks, each followed by an FFN-MoE block on its routing decision (the appendix's
+    RoM + FFN-MoE hybrid without its attention layers), one rom_hybrid_stack_forward call per step."""
+    import torch
+    from paper_2506_18145_amd import RomFfnMoe, RomHybridStack, RomLayer
+    from rom_synth import make_input
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(99)
+    t = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    E, Dm = cfg.n_experts, cfg.d_model
+    normal = lambda shape: (torch.randn(shape, generator=g, device="cuda:0") * cfg.weight_std).to(t)
+    layers = [RomLayer(cfg, device_weights(cfg, 8000 + j), device="cuda:0") for j in range(n_layers)]
+    ffns = []
+    for ly in layers:
+        f = RomFfnMoe(ly, d_ff, {"w_gate_up": normal((E, 2 * d_ff, Dm)), "w_down": normal((E, Dm, d_ff)),
+                                 "norm_w": torch.ones(Dm, device="cuda:0")})
+        f.packed(True, drop_plain=True)
+        ffns.append(f)
+    stack = RomHybridStack(layers, ffns, eps=1e-5, ffn_pre_norm=True, fold_in_place=True)
+    x = layers[0].to_device(make_input(cfg))
+    for _ in range(warmup):
+        out = stack.forward(x)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        out = stack.forward(x)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    return {"workload": f"{n_layers} x (RoM block + FFN-MoE block, d_ff={d_ff}) of {cfg.name}'s shape, one sequence of "
+                        f"{cfg.seq_len} tokens", "ms_per_forward": dt * 1e3, "ms_per_pair": dt * 1e3 / n_layers,
+            "tokens_per_s": cfg.batch * cfg.seq_len / dt, "output_finite": bool(torch.isfinite(out.float()).all().item())}
+
+
 def time_forward(cfg, steps, warmup, calibrate_copy=False):
     """K timed calls of rom_layer_forward on resident inputs.  Returns (ms per call, ms per call
     without the stage events, per-stage dict)."""
@@ -291,6 +324,8 @@ def main():
     ap.add_argument("--no-ffn", action="store_true", help="skip the extra FFN-MoE layer measurement")
     ap.add_argument("--stack-layers", type=int, default=48,
                     help="layers of the extra whole-stack measurement (0 = skip it)")
+    ap.add_argument("--hybrid-layers", type=int, default=0,
+                    help="also time a stack of this many (RoM block + FFN-MoE block) pairs (0 = skip)")
     ap.add_argument("--only-step", action="store_true",
                     help="run only the rom_step measurement and print its JSON object (for profiling)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -347,6 +382,8 @@ def main():
             "stages_ms": {k: v["ms"] for k, v in stages_s.items()}}
     if not args.no_ffn:
         result["ffn_moe"] = ffn_moe_rate(cfg, 2 * cfg.d_model, 20, 20)
+    if args.hybrid_layers > 0:
+        result["hybrid_stack_forward"] = hybrid_stack_rate(cfg, args.hybrid_layers, 2 * cfg.d_model, 3, 1)
     if args.stack_layers > 0:
         result["stack_forward"] = stack_rate(cfg, args.stack_layers, 3, 1)
     if not args.no_step:

@@ -279,6 +279,24 @@ ROM_API int rom_ffn_moe_forward(const rom_dims *dims, int32_t d_ff, const rom_ff
                         const int32_t *offsets, const int32_t *perm, const int32_t *inv_perm,
                         const float *gate, void *out, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* The hybrid of the appendix (RoM + FFN-MoE with shared routing), as a stack: layer j is the RoM
+ * block blocks[j]; if ffns[j].w_gate_up is not NULL an FFN-MoE block (pre-norm if ffn_pre_norm,
+ * always with its skip) follows it and runs on the routing decision that RoM block has just made
+ * - the grouping is picked up from the RoM workspace on the device, nothing visits the host.
+ *   blocks, ffns   host arrays [n_layers]; every FFN has the same d_ff
+ *   tmp            T [B, L, d_model] scratch (needed as soon as the stack has more than one block
+ *                  of either kind); x, out, tmp pairwise distinct
+ *   ws             rom_workspace_bytes(dims, B, L);  ffn_ws  rom_ffn_workspace_bytes(dims, d_ff, B*L),
+ *                  distinct from ws (may be NULL if no layer has an FFN)
+ * States as in rom_stack_forward. */
+ROM_API int rom_hybrid_stack_forward(const rom_dims *dims, int32_t d_ff, const rom_block *blocks,
+                             const rom_ffn_weights *ffns, int ffn_pre_norm, int n_layers, float eps,
+                             const void *x, int64_t B, int64_t L,
+                             const float *conv_state_in, const float *ssm_state_in,
+                             void *out, float *conv_state_out, float *ssm_state_out,
+                             void *tmp, void *ws, size_t ws_bytes, void *ffn_ws, size_t ffn_ws_bytes,
+                             void *hip_stream);
+
 /* Static description of an error code. */
 ROM_API const char *rom_strerror(int code);
 

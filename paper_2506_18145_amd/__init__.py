@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     RomDims,
     RomError,
     RomFfnMoe,
+    RomHybridStack,
     RomLayer,
     RomStack,
     load_library,
@@ -17,6 +18,7 @@ from .binding import (  # noqa: F401
     rom_ffn_moe_forward,
     rom_ffn_workspace_bytes,
     rom_fold_norm,
+    rom_hybrid_stack_forward,
     rom_stack_forward,
     rom_stack_step,
     rom_layer_forward,

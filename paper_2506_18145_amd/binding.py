@@ -91,6 +91,10 @@ def load_library() -> ctypes.CDLL:
     lib.rom_ffn_moe_forward.restype = ctypes.c_int
     lib.rom_ffn_moe_forward.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, ctypes.POINTER(_RomFfnWeights),
                                         ctypes.c_int, F32, ctypes.c_int, P, I64, P, P, P, P, P, P, SZ, P]
+    lib.rom_hybrid_stack_forward.restype = ctypes.c_int
+    lib.rom_hybrid_stack_forward.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, ctypes.POINTER(_RomBlock),
+                                             ctypes.POINTER(_RomFfnWeights), ctypes.c_int, ctypes.c_int, F32, P,
+                                             I64, I64, P, P, P, P, P, P, P, SZ, P, SZ, P]
     lib.rom_strerror.restype = ctypes.c_char_p
     lib.rom_strerror.argtypes = [ctypes.c_int]
     lib.rom_profile_enable.restype = ctypes.c_int
@@ -240,6 +244,15 @@ def rom_ffn_moe_forward(dims, d_ff, w_gate_up, w_down, pre_norm, eps, add_skip, 
         n_tokens, _ptr(offsets), _ptr(perm), _ptr(inv_perm), _ptr(gate), _ptr(out), _ptr(ws), _nbytes(ws),
         _stream())
     _check(code, "rom_ffn_moe_forward")
+
+
+def rom_hybrid_stack_forward(dims, d_ff, blocks, ffns, ffn_pre_norm, eps, x, B, L, conv_state_in, ssm_state_in,
+                             out, conv_state_out, ssm_state_out, tmp, ws, ffn_ws):
+    code = load_library().rom_hybrid_stack_forward(
+        ctypes.byref(dims), d_ff, blocks, ffns, int(bool(ffn_pre_norm)), len(blocks), eps, _ptr(x), B, L,
+        _ptr(conv_state_in), _ptr(ssm_state_in), _ptr(out), _ptr(conv_state_out), _ptr(ssm_state_out),
+        _ptr(tmp), _ptr(ws), _nbytes(ws), _ptr(ffn_ws), _nbytes(ffn_ws), _stream())
+    _check(code, "rom_hybrid_stack_forward")
 
 
 def rom_set_segments(n_segments: int) -> None:
@@ -489,3 +502,45 @@ class RomFfnMoe:
                             pre_norm, self.eps, add_skip, x, n, routing["offsets"], routing["perm"],
                             routing["inv_perm"], routing["gate"], out, self._ws)
         return out
+
+
+class RomHybridStack:
+    """RoM blocks, each optionally followed by an FFN-MoE block that reuses its routing decision
+    (rom_hybrid_stack_forward).  ffns: one RomFfnMoe or None per layer, all of the same d_ff."""
+
+    def __init__(self, layers, ffns, eps: float = 1e-5, ffn_pre_norm: bool = True, fold_in_place: bool = True):
+        if not layers or len(layers) != len(ffns):
+            raise RomError("one (possibly None) FFN-MoE entry per layer")
+        self.layers, self.ffns, self.eps, self.ffn_pre_norm = list(layers), list(ffns), eps, ffn_pre_norm
+        self.dims, self.device = self.layers[0].dims, self.layers[0].device
+        d_ffs = {f.d_ff for f in self.ffns if f is not None}
+        if len(d_ffs) > 1:
+            raise RomError("all FFN-MoE blocks of a stack share one d_ff")
+        self.d_ff = d_ffs.pop() if d_ffs else 16
+        self._keep = [(ly.block_weights(in_place=fold_in_place), ly.weights["norm_w"]) for ly in self.layers]
+        self.blocks = make_blocks(self._keep)
+        self._packed = [None if f is None else f.packed(ffn_pre_norm) for f in self.ffns]
+        self.ffn_structs = (_RomFfnWeights * len(self.ffns))()
+        for j, f in enumerate(self.ffns):
+            if f is not None:
+                self.ffn_structs[j] = _RomFfnWeights(_ptr(self._packed[j]), _ptr(f.w_down))
+        self._tmp: Optional[torch.Tensor] = None
+        self._ffn_ws: Optional[torch.Tensor] = None
+
+    def forward(self, x: torch.Tensor, conv_state=None, ssm_state=None, return_states=False):
+        B, L, _ = x.shape
+        out = torch.empty_like(x)
+        if self._tmp is None or self._tmp.shape != x.shape or self._tmp.dtype != x.dtype:
+            self._tmp = torch.empty_like(x)
+        need = rom_ffn_workspace_bytes(self.dims, self.d_ff, max(B * L, 1))
+        if self._ffn_ws is None or self._ffn_ws.numel() < need:
+            self._ffn_ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+        conv_out = ssm_out = None
+        if return_states:
+            n, d = len(self.layers), self.dims
+            conv_out = torch.empty((n, B, d.d_inner, d.d_conv - 1), dtype=torch.float32, device=self.device)
+            ssm_out = torch.empty((n, B, d.d_inner, d.d_state), dtype=torch.float32, device=self.device)
+        rom_hybrid_stack_forward(self.dims, self.d_ff, self.blocks, self.ffn_structs, self.ffn_pre_norm, self.eps, x,
+                                 B, L, conv_state, ssm_state, out, conv_out, ssm_out, self._tmp,
+                                 self.layers[0].workspace(max(B, 1), max(L, 1)), self._ffn_ws)
+        return (out, conv_out, ssm_out) if return_states else out

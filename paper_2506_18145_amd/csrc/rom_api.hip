@@ -809,6 +809,66 @@ int rom_ffn_moe_forward(const rom_dims *dims, int32_t d_ff, const rom_ffn_weight
   return ROM_OK;
 }
 
+int rom_hybrid_stack_forward(const rom_dims *dims, int32_t d_ff, const rom_block *blocks,
+                             const rom_ffn_weights *ffns, int ffn_pre_norm, int n_layers, float eps,
+                             const void *x, int64_t B, int64_t L, const float *conv_state_in,
+                             const float *ssm_state_in, void *out, float *conv_state_out,
+                             float *ssm_state_out, void *tmp, void *ws, size_t ws_bytes, void *ffn_ws,
+                             size_t ffn_ws_bytes, void *hip_stream) {
+  int rc = check_ffn(dims, d_ff);
+  if (rc != ROM_OK) return rc;
+  if (!blocks || !ffns || n_layers < 1 || B < 0 || L < 0) return ROM_E_INVAL;
+  int n_ops = 0;                        // RoM blocks plus the FFN-MoE blocks behind some of them
+  for (int j = 0; j < n_layers; ++j) {  // refuse the whole call before the first layer is launched
+    rc = check_weights(dims, &blocks[j].w);
+    if (rc != ROM_OK) return rc;
+    if (!blocks[j].norm_weight || !aligned16(blocks[j].norm_weight)) return ROM_E_INVAL;
+    n_ops += 1;
+    if (ffns[j].w_gate_up) {
+      if (!ffns[j].w_down || !aligned16(ffns[j].w_gate_up) || !aligned16(ffns[j].w_down)) return ROM_E_INVAL;
+      n_ops += 1;
+    }
+  }
+  if (n_ops > 1 && (!tmp || tmp == x || tmp == out || !aligned16(tmp))) return ROM_E_INVAL;
+  if (B == 0 || L == 0) return ROM_OK;
+  if (!ws || (n_ops > n_layers && (!ffn_ws || ffn_ws == ws))) return ROM_E_INVAL;
+  const int64_t N = B * L;
+  const Plan p = make_plan(dims, B, L);
+  if (n_ops > n_layers && ffn_ws_bytes < make_ffn_plan(dims, d_ff, N).total) return ROM_E_WORKSPACE;
+  const size_t conv_per = static_cast<size_t>(B) * dims->d_inner * 3, ssm_per = static_cast<size_t>(B) * dims->d_inner * 16;
+  char *base = static_cast<char *>(ws);
+  const void *src = x;
+  int op = 0;
+  auto next_dst = [&]() {               // the blocks write out and tmp in turn, the last one out
+    void *dst = ((n_ops - 1 - op) & 1) ? tmp : out;
+    ++op;
+    return dst;
+  };
+  for (int j = 0; j < n_layers; ++j) {
+    void *dst = next_dst();
+    const BlockOpts blk = {blocks[j].norm_weight, eps};
+    rc = forward_impl(dims, &blocks[j].w, src, B, L, conv_state_in ? conv_state_in + j * conv_per : nullptr,
+                      ssm_state_in ? ssm_state_in + j * ssm_per : nullptr, dst,
+                      conv_state_out ? conv_state_out + j * conv_per : nullptr,
+                      ssm_state_out ? ssm_state_out + j * ssm_per : nullptr, ws, ws_bytes,
+                      static_cast<hipStream_t>(hip_stream), &blk);
+    if (rc != ROM_OK) return rc;
+    src = dst;
+    if (ffns[j].w_gate_up) {
+      // the grouping the RoM block has just left in its workspace drives the FFN-MoE block
+      dst = next_dst();
+      rc = rom_ffn_moe_forward(dims, d_ff, &ffns[j], ffn_pre_norm, eps, 1, src, N,
+                               reinterpret_cast<const int32_t *>(base + p.offsets),
+                               reinterpret_cast<const int32_t *>(base + p.perm),
+                               reinterpret_cast<const int32_t *>(base + p.inv_perm),
+                               reinterpret_cast<const float *>(base + p.gate), dst, ffn_ws, ffn_ws_bytes, hip_stream);
+      if (rc != ROM_OK) return rc;
+      src = dst;
+    }
+  }
+  return ROM_OK;
+}
+
 int rom_stack_step(const rom_dims *dims, const rom_block *blocks, int n_layers, float eps, const void *x,
                    int64_t B, float *conv_state, float *ssm_state, void *out, void *tmp, void *ws,
                    size_t ws_bytes, void *hip_stream) {

@@ -255,3 +255,30 @@ def test_ffn_moe_arguments_and_workspace(lib):
                                    addr, addr + 4096, addr, 4096, None) == -1         # negative eps
     assert lib.rom_ffn_pack_gate_up(ctypes.byref(d), 32, None, addr, addr + 4096, None) == -1
     assert lib.rom_ffn_pack_gate_up(ctypes.byref(d), 32, addr, None, addr, None) == -1     # not in place
+
+
+def test_hybrid_stack_arguments_are_checked_before_any_launch(lib):
+    from paper_2506_18145_amd import binding
+    d = _dims()
+    buf = ctypes.create_string_buffer(8192 + 256)
+    addr = (ctypes.addressof(buf) + 255) // 256 * 256
+    w = binding._RomWeights(*([addr] * 11))
+    blocks = (binding._RomBlock * 2)()
+    for b in blocks:
+        b.w = w
+        b.norm_weight = addr
+    ffns = (binding._RomFfnWeights * 2)()
+    ffns[1] = binding._RomFfnWeights(addr, addr)
+    F = ctypes.c_float
+    call = lambda fw, d_ff=32, tmp=addr + 2048, ffn_ws=addr + 6144, n=2, B=1: lib.rom_hybrid_stack_forward(
+        ctypes.byref(d), d_ff, blocks, fw, 1, n, F(1e-5), addr, B, 8, None, None, addr + 4096, None, None, tmp,
+        addr, 4096, ffn_ws, 1024, None)
+    assert call(ffns, d_ff=24) == -3                       # d_ff not a multiple of 16
+    assert call(None) == -1
+    assert call(ffns, tmp=None) == -1
+    assert call(ffns, ffn_ws=None) == -1                   # layer 1 has an FFN: it needs its workspace
+    assert call(ffns, ffn_ws=addr) == -1                   # ... distinct from the RoM workspace
+    assert call(ffns) == -2                                # everything in place, workspaces too small
+    assert call(ffns, B=0) == 0
+    ffns[1].w_down = None                                  # half an FFN
+    assert call(ffns) == -1

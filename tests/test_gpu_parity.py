@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from oracle import rom_oracle as O
-from paper_2506_18145_amd import RomFfnMoe, RomLayer, RomStack
+from paper_2506_18145_amd import RomFfnMoe, RomHybridStack, RomLayer, RomStack
 from rom_synth import (RomConfig, get_config, make_ffn_weights, make_input, make_stack_weights, make_states,
                        make_weights)
 
@@ -591,3 +591,45 @@ def test_step_and_block_step_replay_from_a_captured_graph():
             assert torch.equal(out_static, eager[t]), f"replay {t}"
             _ = (eager[t].float() * 2).sum().item()             # eager work between the replays
         assert torch.equal(cs, eager_cs) and torch.equal(ss, eager_ss)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_hybrid_stack_of_rom_and_ffn_moe_blocks(dtype):
+    """rom_hybrid_stack_forward: three RoM blocks, the first and the last followed by an FFN-MoE
+    block on their routing decision.  Bit-identical to the same calls made one by one; in fp32
+    (no token of any layer near a routing boundary) equal to the oracle's chain end to end."""
+    n_layers, d_ff = 3, 384
+    cfg = small_cfg(batch=2, seq_len=150, dtype=dtype, n_experts=4, top_k=1, cfg_id=63, weight_std=0.08)
+    ws = make_stack_weights(cfg, n_layers)
+    fws = [make_ffn_weights(small_cfg(cfg_id=63 + 1000 * (j + 1), n_experts=4, dtype=dtype, weight_std=0.08), d_ff)
+           for j in range(n_layers)]
+    has_ffn = [True, False, True]
+    x = make_input(cfg)
+    layers = [RomLayer(cfg, w) for w in ws]
+    ffns = [RomFfnMoe(layers[j], d_ff, fws[j], eps=BLOCK_EPS) if has_ffn[j] else None for j in range(n_layers)]
+    stack = RomHybridStack(layers, ffns, eps=BLOCK_EPS, ffn_pre_norm=True, fold_in_place=False)
+    xd = layers[0].to_device(x)
+    out, conv_s, ssm_s = stack.forward(xd, return_states=True)
+    B, L = cfg.batch, cfg.seq_len
+    N = B * L
+    h = xd
+    for j, ly in enumerate(layers):
+        h, c_j, s_j = ly.block_forward(h, return_states=True, eps=BLOCK_EPS)
+        assert torch.equal(c_j, conv_s[j]) and torch.equal(s_j, ssm_s[j])
+        if has_ffn[j]:
+            routing = {k: ly.ws_view(k, B, L) for k in ("offsets", "perm", "inv_perm", "gate")}
+            h = ffns[j].forward(h, routing, pre_norm=True, add_skip=True)
+    torch.cuda.synchronize()
+    assert torch.equal(h, out)
+    if dtype == "fp32":
+        ref = np.asarray(x, np.float64)
+        for j in range(n_layers):
+            r = O.rom_block_forward(ref, ws[j], cfg.top_k, cfg.gate_mode, BLOCK_EPS)
+            assert np.min(O.topk_margin(r["logits"], cfg.top_k)) > 1e-4
+            ref = r["out"]
+            if has_ffn[j]:
+                ref = O.ffn_moe_forward(ref.reshape(N, -1), fws[j]["w_gate_up"], fws[j]["w_down"], r["expert_idx"],
+                                        r["gate"], fws[j]["norm_w"], BLOCK_EPS, skip=True).reshape(ref.shape)
+            if j == 0:
+                assert np.max(np.abs(ref - r["out"])) > 0.05 * np.max(np.abs(ref))    # the FFN branch is not negligible
+        assert rel_err(to_np(out), ref) <= TOL["fp32"]
