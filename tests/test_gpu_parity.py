@@ -409,7 +409,13 @@ def test_block_small(kw):
     compare_layer(cfg, gpu, x, w, cs, ss, block=True)
 
 
-@pytest.mark.parametrize("name,over", [("cfg1", {}), ("cfg3", dict(batch=1, seq_len=4096))])
+@pytest.mark.parametrize("name,over", [
+    ("cfg1", {}), ("cfg3", dict(batch=1, seq_len=4096)), ("cfg2", {}),
+    # weights large enough that the branch is of the size of the skip term: at the paper-like
+    # initialisations above an error in the fused out projection would hide behind x
+    ("cfg1", dict(weight_std=0.06, cfg_id=85)),
+    ("cfg3", dict(batch=1, seq_len=4096, weight_std=0.05, cfg_id=86)),
+])
 def test_block_big_tile_kernels(name, over):
     """The block at sizes that take the 256-row tiles (row-scaled in projection, out projection
     with the fused skip; the K = 2 case scales in the slot sum and adds the skip in the combine)."""
@@ -526,9 +532,12 @@ def test_ffn_moe_small(kw, d_ff, pre_norm, add_skip, via_forward):
     _ffn_case(small_cfg(weight_std=0.08, **kw), d_ff, pre_norm, add_skip, via_forward)
 
 
-@pytest.mark.parametrize("name,over,d_ff", [("cfg1", {}, 2048), ("cfg3", dict(batch=1, seq_len=4096), 4096)])
+@pytest.mark.parametrize("name,over,d_ff", [("cfg1", {}, 2048), ("cfg3", dict(batch=1, seq_len=4096), 4096),
+                                            ("cfg2", {}, 4096)])
 def test_ffn_moe_big_tile_kernels(name, over, d_ff):
     _ffn_case(get_config(name, **over), d_ff, True, True, True)
+    if name == "cfg1":      # and the branch alone, which the skip term cannot mask
+        _ffn_case(get_config(name, **over), d_ff, True, False, False)
 
 
 @pytest.mark.parametrize("kw", [dict(), dict(dtype="fp32"), dict(top_k=2, gate_mode=1, n_experts=8, cfg_id=73)])
