@@ -361,6 +361,24 @@ def test_step_small():
     _step_run(cfg, 40, tracked=list(range(37)), all_steps=3)
 
 
+def test_random_step_shapes():
+    """Seeded random shapes through rom_step (1 to 1500 sequences, widths off the tile grids, up to
+    64 experts, both dtypes, routed and shared x/dt): four steps each, every sequence against the
+    oracle for the first two, twenty tracked sequences for all four."""
+    import random
+    rng = random.Random(31)
+    for i in range(12):
+        E = rng.choice([1, 2, 3, 5, 8, 12, 16, 33, 64])
+        B = rng.choice([1, 2, 3, 7, 16, 33, 64, 100, 257, 600, 1500])
+        cfg = RomConfig(name=f"random-step-{i}", cfg_id=950 + i, batch=B, seq_len=4, d_model=8 * rng.randint(4, 80),
+                        d_inner=16 * rng.randint(2, 70), d_state=16, d_conv=4,
+                        dt_rank=rng.choice([1, 3, 8, 16, 24, 32, 48, 64, 128]), n_experts=E,
+                        top_k=rng.randint(1, min(E, 4)), dtype=rng.choice(["bf16", "bf16", "fp32"]),
+                        gate_mode=rng.choice([0, 1]), routed_xdt=rng.choice([True, True, False]), weight_std=0.05,
+                        step=True)
+        _step_run(cfg, 4, tracked=list(range(min(B, 20))), all_steps=2)
+
+
 def test_step_matches_forward_last_token():
     """forward(L) followed by one rom_step equals forward(L+1) on its last token."""
     cfg = small_cfg(batch=3, seq_len=65)
