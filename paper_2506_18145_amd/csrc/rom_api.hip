@@ -1,5 +1,7 @@
-// C ABI of librom: argument validation, workspace planning and the launch sequence of the
-// RoM layer forward pass (Eq. (9)-(13)) and its single-token recurrent step.
+// C ABI of librom: argument validation, workspace planning and the launch sequences of the
+// RoM layer forward pass (Eq. (9)-(13)) and its single-token recurrent step, of the pre-norm
+// residual block and stacks of blocks around it, of the FFN-MoE layer that shares the layer's
+// routing decision (appendix Eq. (14), (15)) and of the load-balance statistics (Eq. (16)).
 #include <string.h>
 
 #include "rom_internal.h"

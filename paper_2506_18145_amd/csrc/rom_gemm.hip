@@ -8,6 +8,9 @@
 // BM x BN tile; K is walked in slabs of 64 staged through double-buffered, XOR-swizzled LDS.
 // Group sizes live in device memory: every workgroup finds its (expert, row tile) by walking
 // the offsets, so skewed loads only change how many tiles an expert contributes.
+// Epilogues (compile-time variants): plain store, bias + softplus, per-row scale (gate weight or
+// 1 / rms), per-row scale + skip rows added, fp32 partial sums of inner-dimension slices, and
+// SiLU(gate) * up over a weight whose rows interleave the two halves of a SwiGLU expert.
 // fp32 path (and shapes the MFMA kernel does not take): a plain LDS-tiled FMA kernel.
 #include <type_traits>
 

@@ -1,7 +1,8 @@
 // Sequence-mixing and elementwise kernels of the RoM layer:
 //   causal depthwise conv + SiLU (Eq. (2)), selective scan with D skip and SiLU(z) gating
 //   (Eq. (5), (6)/(13)), the per-token sums over the K selected experts (Eq. (10)/(11)) and the
-//   gate-weighted combine (Eq. (12)).  All of this is bandwidth / plain-ALU work: no MFMA here.
+//   gate-weighted combine (Eq. (12)), plus the small helpers of the FFN-MoE layer (row map,
+//   1 / rms per routed row, SwiGLU for fp32).  All of this is bandwidth / plain-ALU work: no MFMA here.
 #include "rom_internal.h"
 
 namespace rom {
