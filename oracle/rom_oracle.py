@@ -57,14 +57,20 @@ def topk_select(logits, top_k):
 
     Returns idx [N, K] int32 with column k the (k+1)-th largest logit.
     """
-    work = np.array(logits, F64, copy=True)
+    work = np.asarray(logits, F64)
     n = work.shape[0]
     idx = np.empty((n, top_k), np.int32)
     rows = np.arange(n)
+    chosen = np.zeros(work.shape, bool)
     for k in range(top_k):
-        best = np.argmax(work, axis=1)          # first occurrence = lowest index
+        best = np.argmax(np.where(chosen, -np.inf, work), axis=1)   # first occurrence = lowest index
+        # every expert still available sits at -inf (a masking bias): the K picks stay distinct,
+        # the lowest index not yet chosen is next
+        again = chosen[rows, best]
+        if again.any():
+            best[again] = np.argmin(chosen[again], axis=1)
         idx[:, k] = best
-        work[rows, best] = -np.inf
+        chosen[rows, best] = True
     return idx
 
 

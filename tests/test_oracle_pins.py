@@ -64,6 +64,66 @@ def test_routing_hand_worked_example():
     assert inv_perm.tolist() == [int(v) for v in b["inv_perm"][0]]
 
 
+def test_topk_margin_hand_worked_example():
+    """The margin decides which tokens the routing parity tests exempt from the bit-exact check,
+    so it is pinned by hand-worked values (ties, the (K+1)-th gap deciding, K = E)."""
+    b = _read_golden_blocks(os.path.join(GOLDEN, "routing_worked_example.txt"))
+    logits = np.array(b["margin_logits"])
+    for k in (1, 2, 3, 4):
+        assert O.topk_margin(logits, k).tolist() == b[f"margin_k{k}"][0], f"K={k}"
+    # a single expert has no neighbour to be confused with
+    assert np.all(np.isinf(O.topk_margin(logits[:, :1], 1)))
+    # every margin is a gap: never negative
+    rng = np.random.default_rng(5)
+    assert np.all(O.topk_margin(rng.standard_normal((200, 6)), 3) >= 0.0)
+
+
+def test_topk_margin_is_the_perturbation_the_selection_survives():
+    """What the margin means: moving every logit by less than half the margin cannot change the
+    picks or their order; swapping the two logits that realise the margin (a move of exactly the
+    margin) does change them.  A sign slip or an off-by-one in the rank range fails one of the two."""
+    rng = np.random.default_rng(6)
+    n, e = 400, 7
+    logits = rng.standard_normal((n, e))
+    for k in (1, 2, 4, 7):
+        m = O.topk_margin(logits, k)
+        assert np.all(m > 0)
+        base = O.topk_select(logits, k)
+        for _ in range(5):
+            noise = rng.uniform(-0.499, 0.499, (n, e)) * m[:, None]
+            assert np.array_equal(O.topk_select(logits + noise, k), base)
+        # the two neighbours (in sorted order, among the first K+1 ranks) whose gap is the margin
+        order = np.argsort(-logits, axis=1, kind="stable")
+        srt = np.take_along_axis(logits, order, axis=1)
+        hi = min(k + 1, e)
+        gaps = srt[:, :hi - 1] - srt[:, 1:hi]
+        j = np.argmin(gaps, axis=1)
+        assert np.allclose(gaps[np.arange(n), j], m, rtol=0, atol=0)
+        swapped = logits.copy()
+        a, c = order[np.arange(n), j], order[np.arange(n), j + 1]
+        swapped[np.arange(n), a], swapped[np.arange(n), c] = logits[np.arange(n), c], logits[np.arange(n), a]
+        changed = np.any(O.topk_select(swapped, k) != base, axis=1)
+        assert np.all(changed)
+        # gaps beyond rank K+1 do not count: shrinking one of them leaves the margin alone
+        if k + 2 <= e:
+            squeezed = srt.copy()
+            squeezed[:, k + 1] = squeezed[:, k] - 1e-9          # ranks K+1 and K+2 almost tie
+            squeezed[:, k + 2:] -= 10.0
+            assert np.array_equal(O.topk_margin(squeezed, k), m)
+
+
+def test_topk_select_on_a_row_without_finite_order():
+    """NaN logits are outside the layer's contract, but the selection must still name K distinct
+    valid experts (the grouping indexes arrays with them): arg-max treats NaN as the maximum, so
+    an all-NaN row yields experts 0..K-1."""
+    logits = np.full((2, 5), np.nan)
+    logits[1] = [0.0, -np.inf, -np.inf, -np.inf, 1.0]       # fewer finite logits than K
+    idx = O.topk_select(logits, 3)
+    assert idx[0].tolist() == [0, 1, 2]
+    assert idx[1].tolist() == [4, 0, 1]
+    assert all(len(set(r)) == 3 for r in idx.tolist())
+
+
 def test_topk_matches_stable_sort():
     rng = np.random.default_rng(0)
     logits = np.round(rng.standard_normal((500, 7)) * 2) / 2     # many exact ties
