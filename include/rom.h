@@ -4,14 +4,11 @@
  * C ABI.  Every pointer in rom_weights and every tensor / workspace argument is a
  * DEVICE pointer to caller-owned memory unless a comment says "host".  The library
  * allocates no device memory, launches everything asynchronously on the caller's HIP
- * stream (with rom_set_segments >= 2 also on one stream of its own, which it forks from and
- * joins back into the caller's stream inside the call) and never synchronises (the
- * rom_profile_* helpers excepted).  Buffers must stay valid until the stream has passed the
- * end of the call.
- * Because of that a call with rom_set_segments < 2 and profiling off may be recorded into a
- * HIP graph (stream capture) and replayed, once one call of the same shape has run outside a
- * capture: the first use of a kernel that needs more than 64 KiB of LDS sets a function
- * attribute, which is not a stream operation.
+ * stream and never synchronises (the rom_profile_* helpers excepted).  Buffers must stay
+ * valid until the stream has passed the end of the call.
+ * Because of that a call with profiling off may be recorded into a HIP graph (stream capture)
+ * and replayed.  (The first use on a device of a kernel that needs more than 64 KiB of LDS sets
+ * a function attribute - once per device and kernel, thread-safe; it is not a stream operation.)
  *
  * The layer (paper Sec. 4.2, Eq. (9)-(13), on top of the Mamba layer of Sec. 3.1,
  * Eq. (1)-(6)):
@@ -52,6 +49,7 @@ extern "C" {
 #define ROM_E_WORKSPACE   (-2)  /* workspace smaller than rom_workspace_bytes()               */
 #define ROM_E_UNSUPPORTED (-3)  /* shape outside what this build implements (see rom_dims)    */
 #define ROM_E_HIP         (-4)  /* a HIP launch reported an error                             */
+#define ROM_E_STATIC_LIMIT (-5) /* rom_step_static: the call does not fit the static scratch  */
 
 #define ROM_DTYPE_F32  0        /* fp32 weights, activations, arithmetic                      */
 #define ROM_DTYPE_BF16 1        /* bf16 weights/activations, fp32 accumulation and scan state */
@@ -115,6 +113,10 @@ typedef struct rom_ws_layout {
  * host-only; dims is a host pointer. */
 ROM_API size_t rom_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L);
 
+/* Workspace of rom_route alone for N tokens (a few MiB at most: the row map and per-block
+ * histograms of the counting sort); rom_workspace_bytes(dims, N, 1) is an accepted upper bound. */
+ROM_API size_t rom_route_workspace_bytes(const rom_dims *dims, int64_t N);
+
 /* Fills *layout (host) for the same arguments; returns ROM_OK or an error. */
 ROM_API int rom_workspace_layout(const rom_dims *dims, int64_t B, int64_t L, rom_ws_layout *layout);
 
@@ -128,7 +130,7 @@ ROM_API int rom_workspace_layout(const rom_dims *dims, int64_t B, int64_t L, rom
  *                                ascending slot inside an expert)
  *   inv_perm   i32 [N*K]    out  inverse of perm
  *   logits     f32 [N, E]   out, may be NULL
- *   ws/ws_bytes             workspace of at least rom_workspace_bytes(dims, N, 1)
+ *   ws/ws_bytes             workspace of at least rom_route_workspace_bytes(dims, N)
  * N == 0 is a successful no-op.  Errors are reported before anything is launched. */
 ROM_API int rom_route(const rom_dims *dims, const rom_weights *w, const void *x, int64_t N,
               int32_t *expert_idx, float *gate, int32_t *counts, int32_t *offsets,
@@ -175,6 +177,19 @@ ROM_API int rom_layer_forward(const rom_dims *dims, const rom_weights *w, const 
 ROM_API int rom_step(const rom_dims *dims, const rom_weights *w, const void *x, int64_t B,
              float *conv_state, float *ssm_state, void *out,
              void *ws, size_t ws_bytes, void *hip_stream);
+
+/* rom_step for callers that cannot allocate device memory or hold a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and the
+ * same result, bit for bit, as rom_step, minus the workspace: the intermediates live in a
+ * 32 MiB array that is part of the library's device image (one copy per GPU, held until the
+ * process ends).  The call allocates and frees nothing.
+ * Limit: rom_workspace_bytes(dims, B, 1) <= 32 MiB (256 sequences at d_model 2048 with 8 experts
+ * need 11.4 MiB); beyond it the call returns ROM_E_STATIC_LIMIT before anything is launched.
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (different streams
+ * or host threads) race on it; calls queued on one stream do not.  The array keeps the last
+ * call's contents; the step reads no region before writing it, so nothing needs clearing. */
+ROM_API int rom_step_static(const rom_dims *dims, const rom_weights *w, const void *x, int64_t B,
+                    float *conv_state, float *ssm_state, void *out, void *hip_stream);
 
 /* ---- Pre-norm residual block (appendix, architectures overview: every layer sits behind a
  * pre-norm and a skip connection):   out = x + RoM(RMSNorm(x)),
@@ -300,13 +315,12 @@ ROM_API int rom_hybrid_stack_forward(const rom_dims *dims, int32_t d_ff, const r
 /* Static description of an error code. */
 ROM_API const char *rom_strerror(int code);
 
-/* Per-stage timing for benchmarks.  While enabled, rom_layer_forward and rom_step record a pair
- * of HIP events around each stage (kernel or small kernel group) of each segment (see
- * rom_set_segments), on the stream the stage is launched on.  rom_profile_collect synchronises on
- * those events, adds the elapsed milliseconds of every recorded stage into stage_ms (host,
- * ROM_STAGE_COUNT doubles; with more than one segment stages overlap, so their sum exceeds the
- * wall time), stores the number of calls in *n_calls (host) and resets the recorder.
- * max_calls == 0 disables recording and frees the events. */
+/* Per-stage timing for benchmarks.  While enabled, rom_layer_forward and rom_step record a HIP
+ * event at every stage boundary (a stage = a kernel or small kernel group) on the caller's
+ * stream.  rom_profile_collect synchronises on those events, adds the elapsed milliseconds of
+ * every recorded stage into stage_ms (host, ROM_STAGE_COUNT doubles), stores the number of calls
+ * in *n_calls (host) and resets the recorder.  max_calls == 0 disables recording and frees the
+ * events.  Process-wide and not thread-safe: a benchmark's tool, not part of the serving path. */
 #define ROM_STAGE_ROUTE     0  /* router logits, top-K, gates                         */
 #define ROM_STAGE_PERMUTE   1  /* histogram, offsets, stable permutation              */
 #define ROM_STAGE_IN_PROJ   2  /* grouped GEMM, Eq. (10)/(11) (+ sum over k if K > 1)  */
@@ -320,19 +334,6 @@ ROM_API const char *rom_strerror(int code);
 ROM_API int rom_profile_enable(int max_calls);
 ROM_API int rom_profile_collect(double *stage_ms, int *n_calls);
 ROM_API const char *rom_stage_name(int stage);
-
-/* Experimental tuning knob of the forward pass.  A call can be cut into segments (contiguous token
- * ranges: time ranges of a single sequence, whole sequences otherwise) whose stages after the
- * permutation run as a software pipeline on the caller's stream and one stream the library owns,
- * joined back into the caller's stream before the call returns, so that the ALU-bound scan of one
- * segment shares the CUs with the GEMMs of its neighbours.  Results do not depend on the setting
- * beyond floating-point regrouping of the conv / scan carry.
- *   n_segments = 0 or 1: never cut (default: on MI355X the overlap gains nothing measurable),
- *   2..4: cut every call with L >= 2 into that many segments.
- * Process-wide; the library's stream and events are per device and shared by all calls on it:
- * calls that overlap on one device from several host threads race on them.
- * The workspace size depends on this setting: query rom_workspace_bytes after changing it. */
-ROM_API int rom_set_segments(int n_segments);
 
 #ifdef __cplusplus
 }

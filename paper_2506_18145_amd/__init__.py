@@ -24,9 +24,10 @@ from .binding import (  # noqa: F401
     rom_layer_forward,
     rom_profile_collect,
     rom_profile_enable,
-    rom_set_segments,
     rom_route,
+    rom_route_workspace_bytes,
     rom_step,
+    rom_step_static,
     rom_workspace_bytes,
     rom_workspace_layout,
     STAGE_NAMES,

@@ -57,6 +57,8 @@ def load_library() -> ctypes.CDLL:
     P, I64, SZ = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
     lib.rom_workspace_bytes.restype = SZ
     lib.rom_workspace_bytes.argtypes = [ctypes.POINTER(RomDims), I64, I64]
+    lib.rom_route_workspace_bytes.restype = SZ
+    lib.rom_route_workspace_bytes.argtypes = [ctypes.POINTER(RomDims), I64]
     lib.rom_workspace_layout.restype = ctypes.c_int
     lib.rom_workspace_layout.argtypes = [ctypes.POINTER(RomDims), I64, I64, ctypes.POINTER(_RomWsLayout)]
     lib.rom_route.restype = ctypes.c_int
@@ -69,6 +71,8 @@ def load_library() -> ctypes.CDLL:
                                       P, P, P, P, P, P, SZ, P]
     lib.rom_step.restype = ctypes.c_int
     lib.rom_step.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64, P, P, P, P, SZ, P]
+    lib.rom_step_static.restype = ctypes.c_int
+    lib.rom_step_static.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64, P, P, P, P]
     F32 = ctypes.c_float
     lib.rom_fold_norm.restype = ctypes.c_int
     lib.rom_fold_norm.argtypes = [ctypes.POINTER(RomDims), P, P, P, P]
@@ -101,8 +105,6 @@ def load_library() -> ctypes.CDLL:
     lib.rom_profile_enable.argtypes = [ctypes.c_int]
     lib.rom_profile_collect.restype = ctypes.c_int
     lib.rom_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
-    lib.rom_set_segments.restype = ctypes.c_int
-    lib.rom_set_segments.argtypes = [ctypes.c_int]
     lib.rom_stage_name.restype = ctypes.c_char_p
     lib.rom_stage_name.argtypes = [ctypes.c_int]
     _lib = lib
@@ -135,6 +137,10 @@ def _weights_struct(w: Dict[str, Optional[torch.Tensor]]) -> _RomWeights:
 
 def rom_workspace_bytes(dims: RomDims, B: int, L: int) -> int:
     return int(load_library().rom_workspace_bytes(ctypes.byref(dims), B, L))
+
+
+def rom_route_workspace_bytes(dims: RomDims, N: int) -> int:
+    return int(load_library().rom_route_workspace_bytes(ctypes.byref(dims), N))
 
 
 def rom_workspace_layout(dims: RomDims, B: int, L: int) -> Dict[str, int]:
@@ -175,6 +181,13 @@ def rom_step(dims, weights, x, B, conv_state, ssm_state, out, ws):
         _ptr(ssm_state), _ptr(out), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
         _stream())
     _check(code, "rom_step")
+
+
+def rom_step_static(dims, weights, x, B, conv_state, ssm_state, out):
+    code = load_library().rom_step_static(
+        ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(x), B, _ptr(conv_state),
+        _ptr(ssm_state), _ptr(out), _stream())
+    _check(code, "rom_step_static")
 
 
 def _nbytes(t) -> int:
@@ -255,10 +268,6 @@ def rom_hybrid_stack_forward(dims, d_ff, blocks, ffns, ffn_pre_norm, eps, x, B, 
     _check(code, "rom_hybrid_stack_forward")
 
 
-def rom_set_segments(n_segments: int) -> None:
-    _check(load_library().rom_set_segments(n_segments), "rom_set_segments")
-
-
 def rom_profile_enable(max_calls: int) -> None:
     _check(load_library().rom_profile_enable(max_calls), "rom_profile_enable")
 
@@ -295,6 +304,7 @@ class RomLayer:
             t = t.to(self.tdtype) if name in typed else t.to(torch.float32)
             self.weights[name] = t.to(self.device).contiguous()
         self._ws: Optional[torch.Tensor] = None
+        self._route_ws: Optional[torch.Tensor] = None
         self._block_weights: Optional[Dict[str, Optional[torch.Tensor]]] = None
 
     def block_weights(self, in_place: bool = False) -> Dict[str, Optional[torch.Tensor]]:
@@ -378,8 +388,11 @@ class RomLayer:
             "inv_perm": torch.empty((n * d.top_k,), **i32),
             "logits": torch.empty((n, d.n_experts), dtype=torch.float32, device=self.device),
         }
+        need = rom_route_workspace_bytes(d, max(n, 1))
+        if self._route_ws is None or self._route_ws.numel() < need:
+            self._route_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         rom_route(d, self.weights, x, res["expert_idx"], res["gate"], res["counts"], res["offsets"],
-                  res["perm"], res["inv_perm"], res["logits"], self.workspace(max(n, 1), 1))
+                  res["perm"], res["inv_perm"], res["logits"], self._route_ws)
         return res
 
     def balance_stats(self, logits: torch.Tensor, counts: torch.Tensor, alpha: float = 1e-3):
@@ -388,8 +401,11 @@ class RomLayer:
         n = logits.numel() // E
         f32 = dict(dtype=torch.float32, device=self.device)
         frac, mean_prob, loss = torch.empty(E, **f32), torch.empty(E, **f32), torch.empty(1, **f32)
-        rom_balance_stats(self.dims, logits, counts, n, alpha, frac, mean_prob, loss,
-                          self.workspace(max(n, 1), 1))
+        # the call's scratch lies in front of the activation regions of a layer workspace
+        need = rom_workspace_layout(self.dims, max(n, 1), 1)["xz"]
+        if self._route_ws is None or self._route_ws.numel() < need:
+            self._route_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        rom_balance_stats(self.dims, logits, counts, n, alpha, frac, mean_prob, loss, self._route_ws)
         return frac, mean_prob, loss
 
     def forward(self, x: torch.Tensor, conv_state=None, ssm_state=None, return_states=False):

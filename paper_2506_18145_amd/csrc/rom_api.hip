@@ -4,7 +4,15 @@
 // routing decision (appendix Eq. (14), (15)) and of the load-balance statistics (Eq. (16)).
 #include <string.h>
 
+#include <mutex>
+
 #include "rom_internal.h"
+
+// Scratch of rom_step_static: one copy per GPU the library is loaded on, held until the process
+// ends.  Host code never uses this name as an address: the per-device address comes from
+// hipGetSymbolAddress (static_scratch_for_current_device below).
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(32) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace rom {
 namespace {
@@ -12,60 +20,12 @@ namespace {
 constexpr size_t kAlign = 256;
 constexpr size_t kNone = static_cast<size_t>(-1);
 
-// A call can be cut into up to kMaxSegments segments, contiguous token ranges that run the stages
-// after the permutation as a software pipeline on two streams (the caller's and one of the
-// library's), so that the scan of one segment shares the CUs with the GEMMs of its neighbours.
-// One sequence is cut in time (conv and scan state carried from segment to segment), several
-// sequences are dealt out whole.  Routing and the permutation stay global: the permutation is
-// stable, so the slots of a token range are a contiguous sub-range of every expert's group,
-// found by binary search (segment_bounds_kernel).
-// Measured on MI355X at d_model 2048, 16K tokens: co-running kernels slow each other down by
-// what the overlap gains (two segments 1.58 ms against 1.59 ms uncut, more segments are slower),
-// so the automatic setting never cuts; the knob (rom_set_segments) stays for experiments.
-constexpr int kMaxSegments = 4;
-int g_force_segments = 0;            // 0: automatic
-constexpr int kStagger = 1;   // 0: none, 1: a segment starts when the one before has left its conv, 2: ... its dt projection
-
-struct Segments {
-  int n;
-  int64_t tok[kMaxSegments + 1];     // token boundaries, tok[0] = 0, tok[n] = B * L
-  int64_t seq[kMaxSegments + 1];     // sequence boundaries (B > 1) or 0 / 1
-  bool by_time;
-};
-
-Segments plan_segments(const rom_dims *d, int64_t B, int64_t L) {
-  Segments sg;
-  int want = 1;
-  if (g_force_segments > 0) want = g_force_segments;
-  (void)d;
-  if (want > kMaxSegments) want = kMaxSegments;
-  if (L < 2 || B < 1) want = 1;
-  sg.by_time = B == 1;
-  if (sg.by_time) {
-    const int64_t per = ceil_div(ceil_div(L, want), 64) * 64;   // whole scan tiles
-    sg.n = static_cast<int>(ceil_div(L, per));
-    for (int i = 0; i <= sg.n; ++i) {
-      sg.tok[i] = i * per < L ? i * per : L;
-      sg.seq[i] = i == 0 ? 0 : 1;
-    }
-  } else {
-    const int64_t per = ceil_div(B, want);
-    sg.n = static_cast<int>(ceil_div(B, per));
-    for (int i = 0; i <= sg.n; ++i) {
-      sg.seq[i] = i * per < B ? i * per : B;
-      sg.tok[i] = sg.seq[i] * L;
-    }
-  }
-  return sg;
-}
-
 struct Plan {                 // byte offsets inside the workspace
   size_t total;
   size_t expert_idx, gate, counts, offsets, perm, inv_perm, tok_of_pos, block_counts, logits;
   size_t balance_part;        // scratch of rom_balance_stats: placed so that it depends on N, K, E only
   size_t xz, xz_sorted, u, xdbl, dt_low, bc, dt, dt_raw, g, op_sorted, conv_tmp;
-  size_t seg_lo, seg_hi, conv_carry, ssm_carry;
-  size_t scan_q[kMaxSegments], scan_p[kMaxSegments];
+  size_t scan_q, scan_p;      // chunk end states / decays of a time-chunked scan
   size_t rstd;                // f32 [N]: 1 / rms of every token of a pre-norm block's input
   int xproj_slices;           // inner-dimension slices the xdbl buffer has room for
 };
@@ -117,12 +77,7 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   const size_t De = d->d_inner, Dm = d->d_model, R = d->dt_rank;
   const bool multi = K > 1;
   const bool routed_xdt = d->n_experts_xdt > 1;
-  const Segments sg = plan_segments(d, n_seq, seq_len);
-  p.xproj_slices = 1;
-  for (int i = 0; i < sg.n; ++i) {
-    const int n = xproj_slices_for(d, (sg.tok[i + 1] - sg.tok[i]) * (routed_xdt ? d->top_k : 1));
-    if (n > p.xproj_slices) p.xproj_slices = n;
-  }
+  p.xproj_slices = xproj_slices_for(d, n_tok * (routed_xdt ? d->top_k : 1));
   p.expert_idx = take(S * 4);
   p.gate = take(S * 4);
   p.counts = take(E * 4);
@@ -143,94 +98,48 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   p.dt_raw = (multi && routed_xdt) ? take(S * De * b) : kNone;   // per-slot dt pre-activations, in T like every expert output
   p.g = take(N * De * b);
   p.op_sorted = multi ? take(S * Dm * b) : kNone;
-  p.conv_tmp = take(static_cast<size_t>(n_seq) * De * 3 * 4);
-  p.seg_lo = take(kMaxSegments * E * 4);
-  p.seg_hi = take(kMaxSegments * E * 4);
-  const bool carry = sg.n > 1 && sg.by_time;
-  p.conv_carry = carry ? take(2 * De * 3 * 4) : kNone;
-  p.ssm_carry = carry ? take(2 * De * 16 * 4) : kNone;
-  for (int i = 0; i < kMaxSegments; ++i) {
-    size_t bytes = 0;
-    if (i < sg.n)
-      bytes = scan_chunk_state_bytes(sg.by_time ? 1 : sg.seq[i + 1] - sg.seq[i],
-                                     sg.by_time ? sg.tok[i + 1] - sg.tok[i] : seq_len, d->d_inner);
-    p.scan_q[i] = take(bytes);
-    p.scan_p[i] = take(bytes);
-  }
+  // the conv writes its end state beside the old one only when a sequence is cut into runs
+  p.conv_tmp = take(seq_len > kConvInPlaceMaxLen ? static_cast<size_t>(n_seq) * De * 3 * 4 : 0);
+  const size_t chunk_bytes = scan_chunk_state_bytes(n_seq, seq_len, d->d_inner);
+  p.scan_q = take(chunk_bytes);
+  p.scan_p = take(chunk_bytes);
   p.rstd = take(N * 4);
   p.total = off;
   return p;
 }
 
-// ---------------------------------------------------------------- second stream of the pipeline
-// One helper stream and a few events per device, created on first use and kept for the life of
-// the process.  Calls on one device share them: calls that overlap on one device from several
-// host threads race on these events.
-struct Side {
-  bool ready = false;
-  hipStream_t stream = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr, conv_done[kMaxSegments] = {}, dt_done[kMaxSegments] = {},
-             scan_done[kMaxSegments] = {};
-};
-constexpr int kMaxDevices = 32;
-Side g_side[kMaxDevices];
-
-Side *side_for_current_device() {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
-  Side &sd = g_side[dev];
-  if (!sd.ready) {
-    if (hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
-    hipEvent_t *evs[2] = {&sd.fork, &sd.join};
-    for (hipEvent_t *e : evs)
-      if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return nullptr;
-    for (int i = 0; i < kMaxSegments; ++i)
-      if (hipEventCreateWithFlags(&sd.conv_done[i], hipEventDisableTiming) != hipSuccess ||
-          hipEventCreateWithFlags(&sd.dt_done[i], hipEventDisableTiming) != hipSuccess ||
-          hipEventCreateWithFlags(&sd.scan_done[i], hipEventDisableTiming) != hipSuccess)
-        return nullptr;
-    sd.ready = true;
-  }
-  return &sd;
-}
-
 // ---------------------------------------------------------------- stage timing
-// A (begin, end) event pair per call, segment and stage, each recorded on the stream the stage is
-// launched on; begin is recorded after the stage's cross-stream waits.  An uncut call runs its
-// stages back to back on one stream, so there a stage's begin is simply the end of the stage
-// before it (half the events in the timed region).
-constexpr int kProfSlots = kMaxSegments * ROM_STAGE_COUNT * 2;
+// One event per stage boundary of a call: the stages run back to back on one stream, so a
+// stage's begin is the end of the stage before it (event 0 is recorded before the first stage).
+constexpr int kProfEvents = ROM_STAGE_COUNT + 1;
 struct Profiler {
   int max_calls = 0, n_calls = 0;
-  hipEvent_t *ev = nullptr;          // [max_calls][kMaxSegments][ROM_STAGE_COUNT][2]
-  int *begin_of = nullptr;           // [max_calls][kMaxSegments][ROM_STAGE_COUNT]: event index of the begin, -1 = not recorded
+  hipEvent_t *ev = nullptr;          // [max_calls][kProfEvents]
+  int *end_of = nullptr;             // [max_calls][ROM_STAGE_COUNT]: event index of the stage's end, -1 = stage did not run
+  int *begin_of = nullptr;           // same, for its begin
 } g_prof;
 
 struct StageMark {
-  int call;
-  bool on, chained;
-  int last_end;
-  explicit StageMark(bool chain) : call(-1), on(false), chained(chain), last_end(-1) {
+  int call = -1, next = 0, last = -1;
+  bool on = false;
+  StageMark() {
     if (g_prof.ev && g_prof.n_calls < g_prof.max_calls) {
       call = g_prof.n_calls++;
       on = true;
     }
   }
-  void begin(int seg, int stage, hipStream_t s) {
-    if (!on) return;
-    const int slot = call * kProfSlots + (seg * ROM_STAGE_COUNT + stage) * 2;
-    int &b = g_prof.begin_of[call * (kProfSlots / 2) + seg * ROM_STAGE_COUNT + stage];
-    if (chained && last_end >= 0) {
-      b = last_end;
-    } else {
-      (void)hipEventRecord(g_prof.ev[slot], s);
-      b = slot;
-    }
+  void begin(int, hipStream_t s) {
+    if (!on || last >= 0) return;
+    last = call * kProfEvents + next++;
+    (void)hipEventRecord(g_prof.ev[last], s);
   }
-  void end(int seg, int stage, hipStream_t s) {
+  void end(int stage, hipStream_t s) {
     if (!on) return;
-    last_end = call * kProfSlots + (seg * ROM_STAGE_COUNT + stage) * 2 + 1;
-    (void)hipEventRecord(g_prof.ev[last_end], s);
+    const int e = call * kProfEvents + next++;
+    (void)hipEventRecord(g_prof.ev[e], s);
+    g_prof.begin_of[call * ROM_STAGE_COUNT + stage] = last;
+    g_prof.end_of[call * ROM_STAGE_COUNT + stage] = e;
+    last = e;
   }
 };
 
@@ -269,32 +178,6 @@ __global__ void pack_gate_up_kernel(const T *__restrict__ src, const float *__re
   dst[i] = from_f32<T>(scale ? v * scale[d] : v);
 }
 
-struct SegTok {
-  int64_t t[kMaxSegments + 1];
-};
-// seg_lo / seg_hi [segment][expert]: the sorted positions of expert e's slots whose token lies in
-// the segment (tok_of_pos is ascending inside every expert's group)
-__global__ void segment_bounds_kernel(const int32_t *__restrict__ offsets, const int32_t *__restrict__ tok_of_pos,
-                                      int n_experts, int n_seg, SegTok bounds, int32_t *__restrict__ seg_lo,
-                                      int32_t *__restrict__ seg_hi) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n_seg * n_experts) return;
-  const int p = i / n_experts, e = i % n_experts;
-  const int g_lo = offsets[e], g_hi = offsets[e + 1];
-  int64_t want[2] = {bounds.t[p], bounds.t[p + 1]};
-  int res[2];
-  for (int k = 0; k < 2; ++k) {
-    int lo = g_lo, hi = g_hi;
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (tok_of_pos[mid] < want[k]) lo = mid + 1; else hi = mid;
-    }
-    res[k] = lo;
-  }
-  seg_lo[i] = res[0];
-  seg_hi[i] = res[1];
-}
-
 // What turns the layer into the pre-norm, skip-connected block: RMSNorm in front (its scale is
 // folded into w_in by rom_fold_norm; the router applies it itself), the block input added behind.
 struct BlockOpts {
@@ -306,15 +189,15 @@ int route_into(const rom_dims *d, const rom_weights *w, const void *x, int64_t n
                int32_t *expert_idx, float *gate, int32_t *counts, int32_t *offsets, int32_t *perm,
                int32_t *inv_perm, int32_t *tok_of_pos, int32_t *block_counts, float *logits,
                const BlockOpts *blk, float *rstd, hipStream_t s, StageMark *mark) {
-  if (mark) mark->begin(0, ROM_STAGE_ROUTE, s);
+  if (mark) mark->begin(ROM_STAGE_ROUTE, s);
   ROM_TRY(launch_route_topk(d->dtype, x, w->w_router, w->b_router, n_tok, d->d_model, d->n_experts,
                             d->top_k, d->gate_mode, expert_idx, gate, logits, blk ? blk->norm_w : nullptr,
                             blk ? blk->eps : 0.0f, rstd, s));
-  if (mark) mark->end(0, ROM_STAGE_ROUTE, s);
-  if (mark) mark->begin(0, ROM_STAGE_PERMUTE, s);
+  if (mark) mark->end(ROM_STAGE_ROUTE, s);
+  if (mark) mark->begin(ROM_STAGE_PERMUTE, s);
   ROM_TRY(launch_permutation(expert_idx, n_tok * d->top_k, d->n_experts, d->top_k, block_counts,
                              counts, offsets, perm, inv_perm, tok_of_pos, s));
-  if (mark) mark->end(0, ROM_STAGE_PERMUTE, s);
+  if (mark) mark->end(ROM_STAGE_PERMUTE, s);
   return ROM_OK;
 }
 
@@ -334,12 +217,6 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   const int64_t N = B * L;
   Plan p = make_plan(d, B, L);
   if (ws_bytes < p.total) return ROM_E_WORKSPACE;
-  const Segments sg = plan_segments(d, B, L);
-  Side *side = nullptr;
-  if (sg.n > 1) {
-    side = side_for_current_device();
-    if (!side) return ROM_E_HIP;
-  }
 
   char *base = static_cast<char *>(ws);
   auto at = [&](size_t off) { return base + off; };
@@ -350,200 +227,139 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   int32_t *offsets = reinterpret_cast<int32_t *>(at(p.offsets));
   int32_t *inv_perm = reinterpret_cast<int32_t *>(at(p.inv_perm));
   int32_t *tok_of_pos = reinterpret_cast<int32_t *>(at(p.tok_of_pos));
-  int32_t *seg_lo = reinterpret_cast<int32_t *>(at(p.seg_lo));
-  int32_t *seg_hi = reinterpret_cast<int32_t *>(at(p.seg_hi));
   const size_t eb = d->dtype == ROM_DTYPE_BF16 ? 2 : 4;
   const float *rstd = blk ? reinterpret_cast<const float *>(at(p.rstd)) : nullptr;
 
-  StageMark mark(sg.n == 1);
+  StageMark mark;
   rc = route_into(d, w, x, N, reinterpret_cast<int32_t *>(at(p.expert_idx)), gate,
                   reinterpret_cast<int32_t *>(at(p.counts)), offsets, reinterpret_cast<int32_t *>(at(p.perm)),
                   inv_perm, tok_of_pos, reinterpret_cast<int32_t *>(at(p.block_counts)),
                   reinterpret_cast<float *>(at(p.logits)), blk, reinterpret_cast<float *>(at(p.rstd)), s, &mark);
   if (rc != ROM_OK) return rc;
-  if (sg.n > 1) {
-    SegTok st;
-    for (int i = 0; i <= kMaxSegments; ++i) st.t[i] = sg.tok[i <= sg.n ? i : sg.n];
-    hipLaunchKernelGGL(segment_bounds_kernel, dim3(static_cast<unsigned>(ceil_div(sg.n * E, 64))), dim3(64), 0, s,
-                       offsets, tok_of_pos, E, sg.n, st, seg_lo, seg_hi);
-    ROM_TRY(hipGetLastError());
-    ROM_TRY(hipEventRecord(side->fork, s));
-    ROM_TRY(hipStreamWaitEvent(side->stream, side->fork, 0));
-  }
 
-  for (int sgi = 0; sgi < sg.n; ++sgi) {
-    hipStream_t st = (sgi & 1) ? side->stream : s;
-    const int64_t tok0 = sg.tok[sgi], n_tok = sg.tok[sgi + 1] - sg.tok[sgi];
-    const int64_t n_slots = n_tok * K;
-    const int64_t seq0 = sg.by_time ? 0 : sg.seq[sgi];
-    const int64_t n_seq = sg.by_time ? 1 : sg.seq[sgi + 1] - sg.seq[sgi];
-    const int64_t seq_len = sg.by_time ? n_tok : L;
-    const bool first = sgi == 0, last = sgi == sg.n - 1;
-    // the routed GEMMs of a segment: expert e's rows are the sorted positions [lo[e], hi[e])
-    auto routed = [&](GemmArgs &ga) {
-      ga.n_groups = E;
-      ga.M = n_slots;
-      if (sg.n > 1) {
-        ga.offsets = seg_lo + sgi * E;
-        ga.offsets_hi = seg_hi + sgi * E;
-      } else {
-        ga.offsets = offsets;
-      }
-    };
-    // stagger: start this segment's GEMMs beside the previous segment's scan
-    if (!first && kStagger == 2) ROM_TRY(hipStreamWaitEvent(st, side->dt_done[sgi - 1], 0));
-    if (!first && kStagger == 1) ROM_TRY(hipStreamWaitEvent(st, side->conv_done[sgi - 1], 0));
+  // the routed GEMMs: expert e's rows are the sorted positions [offsets[e], offsets[e + 1])
+  auto routed = [&](GemmArgs &ga) {
+    ga.n_groups = E;
+    ga.M = S;
+    ga.offsets = offsets;
+  };
 
-    // in / gate projection, Eq. (10)/(11): gather token rows, scatter back to token order (K == 1)
-    mark.begin(sgi, ROM_STAGE_IN_PROJ, st);
-    GemmArgs ga;
-    memset(&ga, 0, sizeof(ga));
-    ga.dtype = d->dtype;
-    ga.A = x; ga.lda = Dm; ga.a_rows = tok_of_pos; ga.a_span = N * Dm;
-    ga.W = w->w_in; ga.N = 2 * De; ga.K = Dm;
-    routed(ga);
-    ga.C = multi ? at(p.xz_sorted) : at(p.xz); ga.ldc = 2 * De; ga.c_rows = multi ? nullptr : tok_of_pos;
-    // pre-norm block: x @ (W . norm_w)^T scaled by the token's 1/rms is RMSNorm(x) @ W^T
-    if (!multi) ga.row_scale = rstd;
-    ROM_TRY(launch_grouped_gemm(ga, st));
-    if (multi)
-      ROM_TRY(launch_slot_sum(eb == 4, eb == 4, at(p.xz_sorted), 2 * De, at(p.xz) + tok0 * 2 * De * eb, 2 * De,
-                              inv_perm + tok0 * K, n_tok, K, 2 * De, nullptr, 0, rstd ? rstd + tok0 : nullptr, st));
-    mark.end(sgi, ROM_STAGE_IN_PROJ, st);
+  // in / gate projection, Eq. (10)/(11): gather token rows, scatter back to token order (K == 1)
+  mark.begin(ROM_STAGE_IN_PROJ, s);
+  GemmArgs ga;
+  memset(&ga, 0, sizeof(ga));
+  ga.dtype = d->dtype;
+  ga.A = x; ga.lda = Dm; ga.a_rows = tok_of_pos; ga.a_span = N * Dm;
+  ga.W = w->w_in; ga.N = 2 * De; ga.K = Dm;
+  routed(ga);
+  ga.C = multi ? at(p.xz_sorted) : at(p.xz); ga.ldc = 2 * De; ga.c_rows = multi ? nullptr : tok_of_pos;
+  // pre-norm block: x @ (W . norm_w)^T scaled by the token's 1/rms is RMSNorm(x) @ W^T
+  if (!multi) ga.row_scale = rstd;
+  ROM_TRY(launch_grouped_gemm(ga, s));
+  if (multi)
+    ROM_TRY(launch_slot_sum(eb == 4, eb == 4, at(p.xz_sorted), 2 * De, at(p.xz), 2 * De, inv_perm, N, K, 2 * De,
+                            nullptr, 0, rstd, s));
+  mark.end(ROM_STAGE_IN_PROJ, s);
 
-    // short conv + SiLU, Eq. (2).  A time segment takes the three rows before it from the
-    // previous segment's end state (that conv ran before the dt projection waited for above).
-    if (!first && sg.by_time) ROM_TRY(hipStreamWaitEvent(st, side->conv_done[sgi - 1], 0));
-    mark.begin(sgi, ROM_STAGE_CONV, st);
-    {
-      const float *cin = conv_in ? conv_in + seq0 * De * 3 : nullptr;
-      float *cout_final = conv_out ? conv_out + seq0 * De * 3 : nullptr;
-      float *ctmp = reinterpret_cast<float *>(at(p.conv_tmp)) + seq0 * De * 3;
-      // conv_out may alias conv_in (rom_step): a sequence of up to 32 steps is one run of one
-      // thread, which reads the old state before it writes the new one; longer sequences are cut
-      // into runs for different blocks, so the new state goes beside the old one and is copied over
-      float *cdst = cout_final ? ctmp : nullptr;
-      if (cout_final && seq_len <= 32) { cdst = cout_final; cout_final = nullptr; }
-      if (sg.by_time && sg.n > 1) {
-        float *carry = reinterpret_cast<float *>(at(p.conv_carry));
-        if (!first) cin = carry + ((sgi - 1) & 1) * De * 3;
-        if (!last) { cdst = carry + (sgi & 1) * De * 3; cout_final = nullptr; }
-      }
-      ROM_TRY(launch_conv_silu(d->dtype, at(p.xz) + tok0 * 2 * De * eb, 2 * De, w->conv_w, w->conv_b, cin, cdst,
-                               at(p.u) + tok0 * De * eb, n_seq, seq_len, De, st));
-      if (cout_final) {
-        const int64_t n = n_seq * De * 3;
-        hipLaunchKernelGGL(copy_f32_kernel, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, st,
-                           ctmp, cout_final, n);
-        ROM_TRY(hipGetLastError());
-      }
+  // short conv + SiLU, Eq. (2)
+  mark.begin(ROM_STAGE_CONV, s);
+  {
+    // conv_out may alias conv_in (rom_step): a sequence of up to kConvInPlaceMaxLen steps is one
+    // run of one thread, which reads the old state before it writes the new one; longer sequences
+    // are cut into runs for different blocks, so the new state goes beside the old one and is
+    // copied over
+    float *ctmp = reinterpret_cast<float *>(at(p.conv_tmp));
+    float *cdst = conv_out;
+    const bool beside = conv_out && L > kConvInPlaceMaxLen;
+    if (beside) cdst = ctmp;
+    ROM_TRY(launch_conv_silu(d->dtype, at(p.xz), 2 * De, w->conv_w, w->conv_b, conv_in, cdst, at(p.u), B, L, De, s));
+    if (beside) {
+      const int64_t n = B * De * 3;
+      hipLaunchKernelGGL(copy_f32_kernel, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, s, ctmp,
+                         conv_out, n);
+      ROM_TRY(hipGetLastError());
     }
-    mark.end(sgi, ROM_STAGE_CONV, st);
-    if (sg.n > 1) ROM_TRY(hipEventRecord(side->conv_done[sgi], st));
+  }
+  mark.end(ROM_STAGE_CONV, s);
 
-    // x projection -> dt_low | B | C
-    mark.begin(sgi, ROM_STAGE_X_PROJ, st);
-    memset(&ga, 0, sizeof(ga));
-    ga.dtype = d->dtype;
-    ga.lda = De; ga.a_span = N * De;
-    ga.W = w->w_x; ga.N = R + 32; ga.K = De;
-    ga.ldc = R + 32; ga.c_is_f32 = 1;
-    ga.k_splits = xproj_slices_for(d, routed_xdt ? n_slots : n_tok);
-    if (ga.k_splits > p.xproj_slices) ga.k_splits = p.xproj_slices;
-    ga.c_split_stride = (routed_xdt ? S : N) * (R + 32);
-    float *xdbl = reinterpret_cast<float *>(at(p.xdbl));
+  // x projection -> dt_low | B | C
+  mark.begin(ROM_STAGE_X_PROJ, s);
+  memset(&ga, 0, sizeof(ga));
+  ga.dtype = d->dtype;
+  ga.lda = De; ga.a_span = N * De;
+  ga.W = w->w_x; ga.N = R + 32; ga.K = De;
+  ga.ldc = R + 32; ga.c_is_f32 = 1;
+  ga.k_splits = p.xproj_slices;
+  ga.c_split_stride = (routed_xdt ? S : N) * (R + 32);
+  float *xdbl = reinterpret_cast<float *>(at(p.xdbl));
+  ga.A = at(p.u); ga.C = xdbl;
+  if (routed_xdt) {
+    ga.a_rows = tok_of_pos;
+    routed(ga);
+    ga.c_rows = multi ? nullptr : tok_of_pos;
+  } else {
+    ga.n_groups = 1; ga.M = N;
+  }
+  ROM_TRY(launch_grouped_gemm(ga, s));
+  {
+    const bool by_pos = routed_xdt && multi;      // xdbl rows in sorted-slot order, else in token order
+    ROM_TRY(launch_split_xdbl(d->dtype, xdbl, ga.k_splits, ga.c_split_stride, by_pos ? inv_perm : nullptr, K, N, R,
+                              at(p.dt_low), reinterpret_cast<float *>(at(p.bc)), s));
+  }
+  mark.end(ROM_STAGE_X_PROJ, s);
+
+  // dt projection + bias + softplus
+  mark.begin(ROM_STAGE_DT_PROJ, s);
+  memset(&ga, 0, sizeof(ga));
+  ga.dtype = d->dtype;
+  ga.A = at(p.dt_low); ga.lda = R; ga.a_span = N * R;
+  ga.W = w->w_dt; ga.N = De; ga.K = R; ga.ldc = De;
+  if (routed_xdt && multi) {
+    ga.a_rows = tok_of_pos;
+    routed(ga);
+    ga.C = at(p.dt_raw);     // one expert's output per slot, stored in T as in_proj's; summed in fp32 below
+    ROM_TRY(launch_grouped_gemm(ga, s));
+    ROM_TRY(launch_slot_sum(eb == 4, eb == 4, at(p.dt_raw), De, at(p.dt), De, inv_perm, N, K, De, w->dt_bias, 1,
+                            nullptr, s));
+  } else {
+    ga.C = at(p.dt);
     if (routed_xdt) {
-      ga.A = at(p.u); ga.a_rows = tok_of_pos; ga.C = xdbl;
+      ga.a_rows = tok_of_pos; ga.c_rows = tok_of_pos;
       routed(ga);
-      ga.c_rows = multi ? nullptr : tok_of_pos;
     } else {
-      ga.A = at(p.u) + tok0 * De * eb; ga.a_span = n_tok * De; ga.C = xdbl + tok0 * (R + 32);
-      ga.n_groups = 1; ga.M = n_tok;
+      ga.n_groups = 1; ga.M = N;
     }
-    ROM_TRY(launch_grouped_gemm(ga, st));
-    {
-      const bool by_pos = routed_xdt && multi;      // xdbl rows in sorted-slot order, else in token order
-      ROM_TRY(launch_split_xdbl(d->dtype, by_pos ? xdbl : xdbl + tok0 * (R + 32), ga.k_splits, ga.c_split_stride,
-                                by_pos ? inv_perm + tok0 * K : nullptr, K, n_tok, R, at(p.dt_low) + tok0 * R * eb,
-                                reinterpret_cast<float *>(at(p.bc)) + tok0 * 32, st));
-    }
-    mark.end(sgi, ROM_STAGE_X_PROJ, st);
-
-    // dt projection + bias + softplus
-    mark.begin(sgi, ROM_STAGE_DT_PROJ, st);
-    memset(&ga, 0, sizeof(ga));
-    ga.dtype = d->dtype;
-    ga.lda = R; ga.a_span = N * R;
-    ga.W = w->w_dt; ga.N = De; ga.K = R; ga.ldc = De;
-    if (routed_xdt && multi) {
-      ga.A = at(p.dt_low); ga.a_rows = tok_of_pos;
-      routed(ga);
-      ga.C = at(p.dt_raw);     // one expert's output per slot, stored in T as in_proj's; summed in fp32 below
-      ROM_TRY(launch_grouped_gemm(ga, st));
-      ROM_TRY(launch_slot_sum(eb == 4, eb == 4, at(p.dt_raw), De, at(p.dt) + tok0 * De * eb, De, inv_perm + tok0 * K,
-                              n_tok, K, De, w->dt_bias, 1, nullptr, st));
-    } else {
-      if (routed_xdt) {
-        ga.A = at(p.dt_low); ga.a_rows = tok_of_pos; ga.C = at(p.dt); ga.c_rows = tok_of_pos;
-        routed(ga);
-      } else {
-        ga.A = at(p.dt_low) + tok0 * R * eb; ga.a_span = n_tok * R; ga.C = at(p.dt) + tok0 * De * eb;
-        ga.n_groups = 1; ga.M = n_tok;
-      }
-      ga.bias = w->dt_bias; ga.softplus = 1;
-      ROM_TRY(launch_grouped_gemm(ga, st));
-    }
-    mark.end(sgi, ROM_STAGE_DT_PROJ, st);
-    if (sg.n > 1) ROM_TRY(hipEventRecord(side->dt_done[sgi], st));
-
-    // selective scan + D skip + SiLU(z) gate, Eq. (5), (6); a time segment starts from the state
-    // the previous one ended in
-    if (!first && sg.by_time) ROM_TRY(hipStreamWaitEvent(st, side->scan_done[sgi - 1], 0));
-    mark.begin(sgi, ROM_STAGE_SCAN, st);
-    {
-      const float *hin = ssm_in ? ssm_in + seq0 * De * 16 : nullptr;
-      float *hout = ssm_out ? ssm_out + seq0 * De * 16 : nullptr;
-      if (sg.by_time && sg.n > 1) {
-        float *carry = reinterpret_cast<float *>(at(p.ssm_carry));
-        if (!first) hin = carry + ((sgi - 1) & 1) * De * 16;
-        if (!last) hout = carry + (sgi & 1) * De * 16;
-      }
-      const char *z = at(p.xz) + static_cast<size_t>(De) * eb + tok0 * 2 * De * eb;
-      ROM_TRY(launch_scan_gate(d->dtype, at(p.u) + tok0 * De * eb, at(p.dt) + tok0 * De * eb,
-                               reinterpret_cast<const float *>(at(p.bc)) + tok0 * 32, z, 2 * De, w->A_log, w->D, hin,
-                               hout, at(p.g) + tok0 * De * eb, n_seq, seq_len, De,
-                               reinterpret_cast<float *>(at(p.scan_q[sgi])), reinterpret_cast<float *>(at(p.scan_p[sgi])),
-                               st));
-    }
-    mark.end(sgi, ROM_STAGE_SCAN, st);
-    if (sg.n > 1) ROM_TRY(hipEventRecord(side->scan_done[sgi], st));
-
-    // out projection, Eq. (13), and the gate-weighted combine, Eq. (12)
-    mark.begin(sgi, ROM_STAGE_OUT_PROJ, st);
-    memset(&ga, 0, sizeof(ga));
-    ga.dtype = d->dtype;
-    ga.A = at(p.g); ga.lda = De; ga.a_rows = tok_of_pos; ga.a_span = N * De;
-    ga.W = w->w_out; ga.N = Dm; ga.K = De;
-    routed(ga);
-    if (multi) {
-      ga.C = at(p.op_sorted); ga.ldc = Dm;
-      ROM_TRY(launch_grouped_gemm(ga, st));
-      mark.end(sgi, ROM_STAGE_OUT_PROJ, st);
-      mark.begin(sgi, ROM_STAGE_COMBINE, st);
-      ROM_TRY(launch_combine(d->dtype, at(p.op_sorted), inv_perm + tok0 * K, gate + tok0 * K,
-                             static_cast<char *>(out) + tok0 * Dm * eb, n_tok, K, Dm,
-                             blk ? static_cast<const char *>(x) + tok0 * Dm * eb : nullptr, st));
-      mark.end(sgi, ROM_STAGE_COMBINE, st);
-    } else {
-      ga.C = out; ga.ldc = Dm; ga.c_rows = tok_of_pos; ga.row_scale = gate;   // gate[n*1 + 0]
-      if (blk) ga.residual = x;                                               // skip connection
-      ROM_TRY(launch_grouped_gemm(ga, st));
-      mark.end(sgi, ROM_STAGE_OUT_PROJ, st);
-    }
+    ga.bias = w->dt_bias; ga.softplus = 1;
+    ROM_TRY(launch_grouped_gemm(ga, s));
   }
-  if (sg.n > 1) {   // the caller's stream continues when both are done
-    ROM_TRY(hipEventRecord(side->join, side->stream));
-    ROM_TRY(hipStreamWaitEvent(s, side->join, 0));
+  mark.end(ROM_STAGE_DT_PROJ, s);
+
+  // selective scan + D skip + SiLU(z) gate, Eq. (5), (6)
+  mark.begin(ROM_STAGE_SCAN, s);
+  ROM_TRY(launch_scan_gate(d->dtype, at(p.u), at(p.dt), reinterpret_cast<const float *>(at(p.bc)),
+                           at(p.xz) + static_cast<size_t>(De) * eb, 2 * De, w->A_log, w->D, ssm_in, ssm_out, at(p.g), B,
+                           L, De, reinterpret_cast<float *>(at(p.scan_q)), reinterpret_cast<float *>(at(p.scan_p)), s));
+  mark.end(ROM_STAGE_SCAN, s);
+
+  // out projection, Eq. (13), and the gate-weighted combine, Eq. (12)
+  mark.begin(ROM_STAGE_OUT_PROJ, s);
+  memset(&ga, 0, sizeof(ga));
+  ga.dtype = d->dtype;
+  ga.A = at(p.g); ga.lda = De; ga.a_rows = tok_of_pos; ga.a_span = N * De;
+  ga.W = w->w_out; ga.N = Dm; ga.K = De;
+  routed(ga);
+  if (multi) {
+    ga.C = at(p.op_sorted); ga.ldc = Dm;
+    ROM_TRY(launch_grouped_gemm(ga, s));
+    mark.end(ROM_STAGE_OUT_PROJ, s);
+    mark.begin(ROM_STAGE_COMBINE, s);
+    ROM_TRY(launch_combine(d->dtype, at(p.op_sorted), inv_perm, gate, out, N, K, Dm, blk ? x : nullptr, s));
+    mark.end(ROM_STAGE_COMBINE, s);
+  } else {
+    ga.C = out; ga.ldc = Dm; ga.c_rows = tok_of_pos; ga.row_scale = gate;   // gate[n*1 + 0]
+    if (blk) ga.residual = x;                                               // skip connection
+    ROM_TRY(launch_grouped_gemm(ga, s));
+    mark.end(ROM_STAGE_OUT_PROJ, s);
   }
   return ROM_OK;
 }
@@ -583,6 +399,24 @@ FfnPlan make_ffn_plan(const rom_dims *d, int32_t d_ff, int64_t n_tok) {
   return p;
 }
 
+// device address of `scratch` on the current device, looked up once per device
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch_for_current_device(void **out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ROM_E_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return ROM_E_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return ROM_OK;
+}
+
 }  // namespace
 }  // namespace rom
 
@@ -593,6 +427,11 @@ extern "C" {
 size_t rom_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L) {
   if (check_dims(dims) != ROM_OK || B < 0 || L < 0) return 0;
   return make_plan(dims, B > 0 ? B : 1, L > 0 ? L : 1).total;
+}
+
+size_t rom_route_workspace_bytes(const rom_dims *dims, int64_t N) {
+  if (check_dims(dims) != ROM_OK || N < 0) return 0;
+  return make_plan(dims, N > 0 ? N : 1, 1).logits;
 }
 
 int rom_workspace_layout(const rom_dims *dims, int64_t B, int64_t L, rom_ws_layout *layout) {
@@ -629,8 +468,10 @@ int rom_route(const rom_dims *dims, const rom_weights *w, const void *x, int64_t
     return ROM_E_INVAL;
   if ((reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return ROM_E_INVAL;
   if (N * dims->top_k > (1ll << 30)) return ROM_E_UNSUPPORTED;
+  // only the row map and the per-block histograms live in the workspace: the plan's regions up
+  // to the logits (the routing arrays themselves are the caller's)
   Plan p = make_plan(dims, N, 1);
-  if (ws_bytes < p.total) return ROM_E_WORKSPACE;
+  if (ws_bytes < p.logits) return ROM_E_WORKSPACE;
   char *base = static_cast<char *>(ws);
   return route_into(dims, w, x, N, expert_idx, gate, counts, offsets, perm, inv_perm,
                     reinterpret_cast<int32_t *>(base + p.tok_of_pos),
@@ -886,6 +727,24 @@ int rom_step(const rom_dims *dims, const rom_weights *w, const void *x, int64_t 
                       static_cast<hipStream_t>(hip_stream));
 }
 
+int rom_step_static(const rom_dims *dims, const rom_weights *w, const void *x, int64_t B, float *conv_state,
+                    float *ssm_state, void *out, void *hip_stream) {
+  const int rc = check_dims(dims);
+  if (rc != ROM_OK) return rc;
+  if (B < 0) return ROM_E_INVAL;
+  if (B > 0 && (!conv_state || !ssm_state)) return ROM_E_INVAL;
+  if (B > 65535) return ROM_E_UNSUPPORTED;
+  if (B > 0 && make_plan(dims, B, 1).total > kStaticScratchBytes) return ROM_E_STATIC_LIMIT;
+  void *ws = nullptr;
+  if (B > 0) {
+    const int src = static_scratch_for_current_device(&ws);
+    if (src != ROM_OK) return src;
+  }
+  // nothing in the step's workspace has to start at zero: every region is written before it is read
+  return forward_impl(dims, w, x, B, 1, conv_state, ssm_state, out, conv_state, ssm_state, ws, kStaticScratchBytes,
+                      static_cast<hipStream_t>(hip_stream));
+}
+
 const char *rom_strerror(int code) {
   switch (code) {
     case ROM_OK: return "ok";
@@ -893,25 +752,29 @@ const char *rom_strerror(int code) {
     case ROM_E_WORKSPACE: return "workspace too small (see rom_workspace_bytes)";
     case ROM_E_UNSUPPORTED: return "shape not supported by this build (see rom_dims)";
     case ROM_E_HIP: return "a HIP call or kernel launch failed";
+    case ROM_E_STATIC_LIMIT: return "the call needs more scratch than the library's static buffer holds (see rom_step_static)";
     default: return "unknown error code";
   }
 }
 
 int rom_profile_enable(int max_calls) {
   if (g_prof.ev) {
-    for (int i = 0; i < g_prof.max_calls * kProfSlots; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+    for (int i = 0; i < g_prof.max_calls * kProfEvents; ++i) (void)hipEventDestroy(g_prof.ev[i]);
     delete[] g_prof.ev;
     delete[] g_prof.begin_of;
+    delete[] g_prof.end_of;
     g_prof.ev = nullptr;
     g_prof.begin_of = nullptr;
+    g_prof.end_of = nullptr;
   }
   g_prof.max_calls = 0;
   g_prof.n_calls = 0;
   if (max_calls <= 0) return ROM_OK;
-  const int n = max_calls * kProfSlots;
+  const int n = max_calls * kProfEvents;
   g_prof.ev = new hipEvent_t[n];
-  g_prof.begin_of = new int[n / 2];
-  for (int i = 0; i < n / 2; ++i) g_prof.begin_of[i] = -1;
+  g_prof.begin_of = new int[max_calls * ROM_STAGE_COUNT];
+  g_prof.end_of = new int[max_calls * ROM_STAGE_COUNT];
+  for (int i = 0; i < max_calls * ROM_STAGE_COUNT; ++i) g_prof.begin_of[i] = g_prof.end_of[i] = -1;
   for (int i = 0; i < n; ++i)
     if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) return ROM_E_HIP;
   g_prof.max_calls = max_calls;
@@ -923,24 +786,17 @@ int rom_profile_collect(double *stage_ms, int *n_calls) {
   for (int i = 0; i < ROM_STAGE_COUNT; ++i) stage_ms[i] = 0.0;
   *n_calls = g_prof.n_calls;
   for (int c = 0; c < g_prof.n_calls; ++c) {
-    for (int i = 0; i < kProfSlots / 2; ++i) {
-      int &b = g_prof.begin_of[c * (kProfSlots / 2) + i];
-      if (b < 0) continue;
-      hipEvent_t end = g_prof.ev[c * kProfSlots + i * 2 + 1];
-      if (hipEventSynchronize(end) != hipSuccess) return ROM_E_HIP;
+    for (int i = 0; i < ROM_STAGE_COUNT; ++i) {
+      int &b = g_prof.begin_of[c * ROM_STAGE_COUNT + i], &e = g_prof.end_of[c * ROM_STAGE_COUNT + i];
+      if (b < 0 || e < 0) continue;
+      if (hipEventSynchronize(g_prof.ev[e]) != hipSuccess) return ROM_E_HIP;
       float ms = 0.0f;
-      if (hipEventElapsedTime(&ms, g_prof.ev[b], end) != hipSuccess) return ROM_E_HIP;
-      stage_ms[i % ROM_STAGE_COUNT] += ms;
-      b = -1;
+      if (hipEventElapsedTime(&ms, g_prof.ev[b], g_prof.ev[e]) != hipSuccess) return ROM_E_HIP;
+      stage_ms[i] += ms;
+      b = e = -1;
     }
   }
   g_prof.n_calls = 0;
-  return ROM_OK;
-}
-
-int rom_set_segments(int n_segments) {
-  if (n_segments < 0 || n_segments > kMaxSegments) return ROM_E_INVAL;
-  g_force_segments = n_segments;
   return ROM_OK;
 }
 

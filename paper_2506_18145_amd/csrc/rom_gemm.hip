@@ -12,6 +12,8 @@
 // 1 / rms), per-row scale + skip rows added, fp32 partial sums of inner-dimension slices, and
 // SiLU(gate) * up over a weight whose rows interleave the two halves of a SwiGLU expert.
 // fp32 path (and shapes the MFMA kernel does not take): a plain LDS-tiled FMA kernel.
+#include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "rom_internal.h"
@@ -79,7 +81,7 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmArgs &a, int BM, int 
   } else {
     int rem = mt;
     for (int e = 0; e < a.n_groups; ++e) {
-      const int lo = a.offsets[e], hi = a.offsets_hi ? a.offsets_hi[e] : a.offsets[e + 1];
+      const int lo = a.offsets[e], hi = a.offsets[e + 1];
       const int tiles = (hi - lo + BM - 1) / BM;
       if (rem < tiles) {
         tc.group = e;
@@ -843,6 +845,27 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const GemmArgs a) {
   }
 }
 
+// A kernel that asks for more than 64 KiB of dynamic LDS needs a function attribute, set once
+// per device (the attribute belongs to the device's copy of the code object).  One instance per
+// kernel instantiation; safe to call from several host threads.
+constexpr int kAttrMaxDevices = 64;
+struct LdsAttrOnce {
+  std::mutex mu;
+  std::atomic<bool> done[kAttrMaxDevices] = {};
+  hipError_t ensure(const void *kernel, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kAttrMaxDevices) return hipErrorInvalidDevice;
+    if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done[dev].load(std::memory_order_relaxed)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done[dev].store(true, std::memory_order_release);
+    return e;
+  }
+};
+
 int grid_tiles(const GemmArgs &a, int BM, int BN) {
   const int64_t m_tiles = a.offsets ? (a.M / BM + a.n_groups) : ceil_div(a.M, BM);
   const int64_t n_tiles = ceil_div(a.N, BN);
@@ -858,14 +881,10 @@ hipError_t launch_mfma_k(const GemmArgs &a, hipStream_t s) {
   constexpr int kLoopSmem = 2 * (BM + BN) * kRowChunks * 16;
   constexpr int kStageSmem = EPI == kEpiPlainF32 ? 0 : WM * WN * 32 * ((BN / WN) * 2 + 16);
   constexpr int kSmem = kLoopSmem > kStageSmem ? kLoopSmem : kStageSmem;
-  static bool attr_set = false;   // per instantiation
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(
-        reinterpret_cast<const void *>(&gemm_bf16_mfma_kernel<BM, BN, WM, WN, EPI, KTAIL>),
-        hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttrOnce attr;         // per instantiation
+  const hipError_t e =
+      attr.ensure(reinterpret_cast<const void *>(&gemm_bf16_mfma_kernel<BM, BN, WM, WN, EPI, KTAIL>), kSmem);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((gemm_bf16_mfma_kernel<BM, BN, WM, WN, EPI, KTAIL>),
                      dim3(grid_tiles(a, BM, BN), a.k_splits), dim3(WM * WN * 64), kSmem, s, a);
   return hipGetLastError();
@@ -879,13 +898,9 @@ hipError_t launch_mfma(const GemmArgs &a, hipStream_t s) {
 template <int KSTEPS, bool PLAIN>
 hipError_t launch_smallk(const GemmArgs &a, hipStream_t s) {
   constexpr int kSmem = kSkBN * KSTEPS * 2 * 16 + kSkBN * 4 + kSkWaves * 32 * (kSkBN + 16);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_smallk_kernel<KSTEPS, PLAIN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttrOnce attr;
+  const hipError_t e = attr.ensure(reinterpret_cast<const void *>(&gemm_bf16_smallk_kernel<KSTEPS, PLAIN>), kSmem);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((gemm_bf16_smallk_kernel<KSTEPS, PLAIN>), dim3(grid_tiles(a, kSkBM, kSkBN)), dim3(kSkWaves * 64), kSmem, s, a);
   return hipGetLastError();
 }
@@ -893,13 +908,9 @@ hipError_t launch_smallk(const GemmArgs &a, hipStream_t s) {
 template <int BN, int WM, int WN, int EPI>
 hipError_t launch_dma(const GemmArgs &a, hipStream_t s) {
   constexpr int kSmem = kDmaSlots * 256 * kDmaRC * 16;     // 160 KiB
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<BN, WM, WN, EPI>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttrOnce attr;
+  const hipError_t e = attr.ensure(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<BN, WM, WN, EPI>), kSmem);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((gemm_bf16_dma_kernel<BN, WM, WN, EPI>), dim3(grid_tiles(a, 256, BN), a.k_splits),
                      dim3(WM * WN * 64), kSmem, s, a);
   return hipGetLastError();

@@ -66,8 +66,7 @@ struct GemmArgs {
   const int32_t *a_rows;     // row of A for position p, NULL = p
   int64_t a_span;            // number of elements of A that may be addressed (rows * lda)
   const void *W;             // [n_groups, N, K] row-major
-  const int32_t *offsets;    // NULL = single group; group e is the rows [offsets[e], offsets[e + 1]) ...
-  const int32_t *offsets_hi; // ... or, if not NULL, [offsets[e], offsets_hi[e]) (device, i32 [n_groups])
+  const int32_t *offsets;    // NULL = single group; group e is the rows [offsets[e], offsets[e + 1]) (device, i32 [n_groups+1])
   int n_groups;
   int64_t M;                 // total rows (positions)
   int N, K;                  // out features, in features
@@ -103,6 +102,8 @@ hipError_t launch_split_xdbl(int dtype, const float *xdbl, int n_slices, int64_t
                              void *dt_low, float *bc, hipStream_t s);
 // number of inner-dimension slices the x projection is cut into (small batches only)
 int xproj_k_splits(int64_t rows, int n_groups, int d_inner);
+// a sequence of at most this many steps is one run of one conv thread: its state may be updated in place
+constexpr int kConvInPlaceMaxLen = 32;
 hipError_t launch_conv_silu(int dtype, const void *xz, int64_t ld_xz, const float *conv_w,
                             const float *conv_b, const float *state_in, float *state_out, void *u,
                             int64_t B, int64_t L, int d_inner, hipStream_t s);

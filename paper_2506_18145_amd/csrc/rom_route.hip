@@ -183,18 +183,26 @@ __global__ __launch_bounds__(256) void route_topk_kernel(
     const float p_un = (lane < n_experts) ? __expf(mine - lmax) : 0.0f;
     const float denom = wave_sum(p_un);
 
-    float work = mine;
+    // K rounds of arg-max over the experts not yet picked.  The picked set is kept apart from
+    // the values, and a round in which no candidate compares equal to the maximum (NaN logits:
+    // the max drops them) or every candidate sits at -inf (a masking bias) takes the lowest
+    // candidate, so that every round names a valid expert and the K picks are distinct - the
+    // grouping kernels index arrays with them.  A NaN logit still gives a NaN gate and a NaN
+    // output row for that token, nothing worse.
+    bool picked = false;
     float my_gate = 0.0f;       // lane k ends up with the gate of the k-th pick
     int my_pick = 0;
     float picked_sum = 0.0f;
     for (int k = 0; k < top_k; ++k) {
-      const float best = wave_max(work);
-      const unsigned long long hit = __ballot(work == best && lane < n_experts);
+      const bool cand = lane < n_experts && !picked;
+      const float best = wave_max(cand ? mine : -INFINITY);
+      unsigned long long hit = __ballot(cand && mine == best);
+      if (hit == 0ull) hit = __ballot(cand);
       const int e_sel = __ffsll(static_cast<long long>(hit)) - 1;   // lowest index wins ties
       const float p_sel = __shfl(p_un, e_sel, kWave);
       picked_sum += p_sel;
       if (lane == k) { my_pick = e_sel; my_gate = p_sel; }
-      if (lane == e_sel) work = -INFINITY;
+      if (lane == e_sel) picked = true;
     }
     if (lane < top_k) {
       const float norm = (gate_mode == 1) ? picked_sum : denom;
@@ -285,7 +293,7 @@ __global__ __launch_bounds__(kSortBlock) void scatter_kernel(
   const int key = (s < n_slots) ? expert_idx[s] : -1;
   const unsigned long long same = match_expert(key, n_experts, lane, cnt[wave]);
   __syncthreads();
-  if (s >= n_slots) return;
+  if (s >= n_slots || key < 0 || key >= n_experts) return;      // (a key outside [0, E) is never written by the router)
   const unsigned long long below = same & ((1ull << lane) - 1ull);
   int pos = offsets[key] + block_base[static_cast<int64_t>(blockIdx.x) * n_experts + key] +
             __popcll(below);
@@ -335,7 +343,7 @@ __global__ __launch_bounds__(kSortBlock) void permutation_small_kernel(
     const int key = s < n_slots ? expert_idx[s] : -1;
     const unsigned long long same = match_expert(key, n_experts, lane, cnt[wave]);
     __syncthreads();
-    if (s < n_slots) {
+    if (s < n_slots && key >= 0 && key < n_experts) {
       int pos = base[key] + __popcll(same & ((1ull << lane) - 1ull));
       for (int w = 0; w < wave; ++w) pos += cnt[w][key];
       inv_perm[s] = pos;

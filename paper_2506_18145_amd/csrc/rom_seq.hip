@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) void split_xdbl_kernel(const float *__restrict
 // ------------------------------------------------------------------ conv + SiLU, Eq. (2)
 // A thread owns one 16-byte group of channels and walks kConvRun consecutive time steps with the
 // last three inputs in registers, so every input row is read once (plus a 3-row halo per run).
-constexpr int kConvRun = 32;
+constexpr int kConvRun = kConvInPlaceMaxLen;
 
 template <typename T>
 __global__ __launch_bounds__(256) void conv_silu_kernel(
@@ -406,7 +406,7 @@ __device__ __forceinline__ void scan_park(ScanSmem &sm, const ScanStage<T> &r, i
 }
 
 // grid: (d_inner / 16, B, chunks handled by this pass).  chunk_q / chunk_p: f32
-// [B][n_chunks - 1][d_inner][16], end state from zero and total decay of every chunk but the last.
+// [B][n_chunks][d_inner][16], end state from zero and total decay of every chunk but the last.
 // NB = 1: one tile in LDS (24 KiB, six blocks per CU); NB = 2: two tiles and two g tiles (58 KiB):
 // the next tile is parked while this one is computed and a tile costs one barrier instead of two,
 // which pays when the launch has no more than one block per CU anyway.
@@ -436,11 +436,19 @@ __global__ __launch_bounds__(256) void scan_kernel(
 
   const float a2 = -__expf(A_log[static_cast<int64_t>(ch) * 16 + n]) * 1.44269504088896341f;
   const float d_skip = kStateOnly ? 0.0f : D[ch];
+  // chunk_q / chunk_p hold n_chunks slots per sequence: slots 0..n_chunks-2 the chunk summaries,
+  // the last slot of chunk_q a copy of the incoming state taken by the state-only pass, so that
+  // the full pass of a chunked launch never reads h_in (h_out may alias it, and the last chunk's
+  // block writes h_out while blocks of earlier chunks may still be starting)
   float h = 0.0f;
-  if (!kStateOnly) {
-    h = h_in ? h_in[(b * d_inner + ch) * 16 + n] : 0.0f;
+  if (kStateOnly) {
+    if (chunk == 0)
+      chunk_q[((b * n_chunks + (n_chunks - 1)) * d_inner + ch) * 16 + n] = h_in ? h_in[(b * d_inner + ch) * 16 + n] : 0.0f;
+  } else {
+    if (n_chunks > 1) h = chunk_q[((b * n_chunks + (n_chunks - 1)) * d_inner + ch) * 16 + n];
+    else h = h_in ? h_in[(b * d_inner + ch) * 16 + n] : 0.0f;
     for (int k = 0; k < chunk; ++k) {      // fold the chunks before this one
-      const int64_t at = ((b * (n_chunks - 1) + k) * d_inner + ch) * 16 + n;
+      const int64_t at = ((b * n_chunks + k) * d_inner + ch) * 16 + n;
       h = fmaf(chunk_p[at], h, chunk_q[at]);
     }
   }
@@ -518,7 +526,7 @@ __global__ __launch_bounds__(256) void scan_kernel(
     }
   }
   if (kStateOnly) {
-    const int64_t at = ((b * (n_chunks - 1) + chunk) * d_inner + ch) * 16 + n;
+    const int64_t at = ((b * n_chunks + chunk) * d_inner + ch) * 16 + n;
     chunk_q[at] = h;
     chunk_p[at] = fast_exp2(a2 * row_sum16(dt_sum));
   } else if (h_out && chunk == n_chunks - 1) {
@@ -827,7 +835,7 @@ int scan_chunks(int64_t B, int64_t L, int d_inner) {
 
 size_t scan_chunk_state_bytes(int64_t B, int64_t L, int d_inner) {
   const int nc = scan_chunks(B, L, d_inner);
-  return static_cast<size_t>(B) * (nc > 1 ? nc - 1 : 0) * d_inner * 16 * sizeof(float);
+  return static_cast<size_t>(B) * (nc > 1 ? nc : 0) * d_inner * 16 * sizeof(float);
 }
 
 template <typename T>
@@ -847,7 +855,7 @@ static hipError_t scan_dispatch(const T *u, const T *dt, const float *bc, const 
   const unsigned gx = static_cast<unsigned>(d_inner / kScanCh), gy = static_cast<unsigned>(B);
   if (nc > 1) {
     hipLaunchKernelGGL((scan_kernel<T, true, 1>), dim3(gx, gy, nc - 1), dim3(256), 0, s, u, dt, bc,
-                       static_cast<const T *>(nullptr), ld_z, A_log, D, static_cast<const float *>(nullptr),
+                       static_cast<const T *>(nullptr), ld_z, A_log, D, h_in,
                        static_cast<float *>(nullptr), static_cast<T *>(nullptr), L, d_inner, chunk_len, nc,
                        chunk_q, chunk_p);
   }

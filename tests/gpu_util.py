@@ -12,6 +12,14 @@ from rom_synth import make_input, make_weights
 # max |gpu - ref| / max |ref| per tensor
 TOL = {"fp32": 1e-4, "bf16": 2e-2}
 MARGIN = 1e-5     # tokens whose top-K logit margin is below this are excluded from the exact-index check
+# Per element, with a floor: max_i |gpu_i - ref_i| / (|ref_i| + rms(ref)).  The tensor-normalised
+# figure above lets an error hide in small-magnitude regions next to a few large elements; this one
+# holds every element to its own size, down to the tensor's rms (a plain elementwise ratio has no
+# meaning at zero crossings).  An element of typical size carries the same rounding error as the
+# tensor maximum does relative to itself, but the errors of the bf16 intermediates it was computed
+# from scale with *their* typical size, so the ratio is a few times the normalised figure: the
+# bound is 2.5 x TOL, and the measured value is printed next to it.
+ELEM_TOL = {"fp32": 2.5e-4, "bf16": 5e-2}
 
 
 def rel_err(got, ref) -> float:
@@ -19,6 +27,39 @@ def rel_err(got, ref) -> float:
     ref = np.asarray(ref, np.float64)
     scale = np.max(np.abs(ref))
     return float(np.max(np.abs(got - ref)) / (scale if scale > 0 else 1.0))
+
+
+def elem_err(got, ref) -> float:
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    if rms == 0.0:
+        return float(np.max(np.abs(got - ref)))
+    return float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
+
+
+def col_err(got, ref) -> float:
+    """Worst column of a [rows, columns] tensor, each column normalised by its own maximum: for
+    tensors whose columns live on different scales (dt spans two decades across channels)."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    scale = np.max(np.abs(ref), axis=0)
+    scale = np.where(scale > 0, scale, 1.0)
+    return float(np.max(np.max(np.abs(got - ref), axis=0) / scale))
+
+
+def max_excluded(logits, top_k: int) -> int:
+    """How many tokens the margin band may exempt from the exact-index check before the check
+    counts as vacuous.  For continuous logits of spread sigma the density of an expert's logit
+    is at most 0.4 / sigma, so a given neighbour gap is below MARGIN with probability at most
+    MARGIN * E * 0.4 / sigma; K gaps per token, a factor 3 of slack, plus 2: a handful of the
+    16K tokens of the paper-shaped workloads (measured: 0 or 1), a few percent only at 64
+    experts with top-8 on narrow logits."""
+    logits = np.asarray(logits, np.float64)
+    n, e = logits.shape
+    sigma = float(np.median(np.std(logits, axis=0))) if n > 1 else 1.0
+    sigma = max(sigma, 1e-3)
+    return 2 + int(3.0 * n * top_k * e * 0.4 * MARGIN / sigma)
 
 
 def to_np(t: torch.Tensor) -> np.ndarray:
@@ -42,6 +83,8 @@ def check_routing(cfg, gpu, x_np, w_np, block=False):
     own = O.topk_select(logits, cfg.top_k)
     close = O.topk_margin(logits, cfg.top_k) < MARGIN
     idx = gpu["expert_idx"].astype(np.int32)
+    assert int(close.sum()) <= max_excluded(logits, cfg.top_k), \
+        f"{int(close.sum())} of {n_tok} tokens inside the margin band"
     assert np.array_equal(idx[~close], own[~close]), "expert assignment differs outside the margin band"
     # whatever the GPU chose for the excluded tokens must still be K distinct valid experts
     assert idx.min() >= 0 and idx.max() < cfg.n_experts
@@ -70,12 +113,20 @@ def run_layer(cfg, conv_state=None, ssm_state=None, x_np=None, w_np=None, return
     x = layer.to_device(x_np)
     cs = None if conv_state is None else layer.to_device(conv_state, typed=False)
     ss = None if ssm_state is None else layer.to_device(ssm_state, typed=False)
+    B, L = x.shape[0], x.shape[1]
+    # the workspace sits between two canary pads: the call may touch rom_workspace_bytes() bytes only
+    from paper_2506_18145_amd import rom_workspace_bytes
+    need, pad = rom_workspace_bytes(layer.dims, max(B, 1), max(L, 1)), 4096
+    guarded = torch.full((need + 2 * pad,), 0xA5, dtype=torch.uint8, device=layer.device)
+    layer._ws = guarded[pad:pad + need]
     if block:
         out, conv_out, ssm_out = layer.block_forward(x, cs, ss, return_states=True, eps=BLOCK_EPS)
     else:
         out, conv_out, ssm_out = layer.forward(x, cs, ss, return_states=True)
     torch.cuda.synchronize()
-    B, L = x.shape[0], x.shape[1]
+    assert layer._ws.data_ptr() == guarded.data_ptr() + pad, "the layer replaced the guarded workspace"
+    assert bool((guarded[:pad] == 0xA5).all()) and bool((guarded[pad + need:] == 0xA5).all()), \
+        "a kernel wrote outside the workspace"
     gpu = {name: to_np(layer.ws_view(name, B, L)) for name in
            ("expert_idx", "gate", "counts", "offsets", "perm", "inv_perm", "logits", "xz", "u", "dt_low",
             "bc", "dt", "g")}
@@ -91,16 +142,18 @@ def compare_layer(cfg, gpu, x_np, w_np, conv_state=None, ssm_state=None, stages=
     else:
         ref = O.rom_layer_forward(x_np, w_np, cfg.top_k, cfg.gate_mode, conv_state, ssm_state, expert_idx=idx)
     tol = TOL[cfg.dtype]
-    errs = {}
+    errs, elem = {}, {}
     if stages:
         r = cfg.dt_rank
-        errs["xz"] = rel_err(gpu["xz"], ref["xz"])
-        errs["u"] = rel_err(gpu["u"], ref["u"])
-        errs["dt_low"] = rel_err(gpu["dt_low"], ref["xdbl"][:, :r])
-        errs["bc"] = rel_err(gpu["bc"], ref["xdbl"][:, r:])
-        errs["dt"] = rel_err(gpu["dt"], ref["dt"])
-        errs["g"] = rel_err(gpu["g"], ref["g"])
+        pairs = {"xz": (gpu["xz"], ref["xz"]), "u": (gpu["u"], ref["u"]),
+                 "dt_low": (gpu["dt_low"], ref["xdbl"][:, :r]), "bc": (gpu["bc"], ref["xdbl"][:, r:]),
+                 "dt": (gpu["dt"], ref["dt"]), "g": (gpu["g"], ref["g"])}
+        for name, (got, want) in pairs.items():
+            errs[name] = rel_err(got, want)
+            elem[name] = elem_err(got, want)
+        errs["dt/col"] = col_err(gpu["dt"], ref["dt"])       # every channel's dt at its own scale
     errs["out"] = rel_err(gpu["out"], ref["out"])
+    elem["out"] = elem_err(gpu["out"], ref["out"])
     if block:
         # the branch alone, so that an error in it cannot hide behind a large skip term; the
         # output's own rounding (unit roundoff of the activation type: 8 significant bits in
@@ -112,7 +165,10 @@ def compare_layer(cfg, gpu, x_np, w_np, conv_state=None, ssm_state=None, stages=
     errs["ssm_state"] = rel_err(gpu["ssm_state"], ref["ssm_state"])
     errs["conv_state"] = rel_err(gpu["conv_state"], ref["conv_state"])
     print(f"[{cfg.name}] excluded={n_excl} counts={gpu['counts'].tolist()} "
-          + " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+          + " ".join(f"{k}={v:.2e}" for k, v in errs.items())
+          + " | per element (rms floor): " + " ".join(f"{k}={v:.2e}" for k, v in elem.items()), flush=True)
     bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, f"beyond tolerance {tol}: {bad}"
+    bad = {k: v for k, v in elem.items() if not v <= ELEM_TOL[cfg.dtype]}
+    assert not bad, f"per-element error beyond {ELEM_TOL[cfg.dtype]}: {bad}"
     return ref, errs

@@ -132,30 +132,19 @@ def test_binding_refuses_to_run_without_a_gpu():
         RomLayer(cfg, make_weights(cfg))
 
 
-def test_segment_knob_is_validated_and_keeps_the_workspace_plan_consistent(lib):
+def test_route_workspace_is_small_and_the_layer_workspace_an_upper_bound(lib):
     from paper_2506_18145_amd import binding
-    d = _dims(dtype=1, d_model=256, d_inner=512, dt_rank=16)
-    base = binding.rom_workspace_bytes(d, 1, 1000)
-    try:
-        binding.rom_set_segments(1)
-        assert binding.rom_workspace_bytes(d, 1, 1000) == base          # 0 and 1: never cut
-        binding.rom_set_segments(3)
-        cut = binding.rom_workspace_bytes(d, 1, 1000)
-        assert cut > 0
-        binding.rom_set_segments(0)
-        steps = binding.rom_workspace_bytes(d, 4, 1)
-        binding.rom_set_segments(3)
-        assert binding.rom_workspace_bytes(d, 4, 1) == steps                # single steps are never cut
-        lay = binding.rom_workspace_layout(d, 1, 1000)
-        assert lay["total_bytes"] == cut
-        with pytest.raises(binding.RomError):
-            binding.rom_set_segments(5)
-        with pytest.raises(binding.RomError):
-            binding.rom_set_segments(-1)
-    finally:
-        binding.rom_set_segments(0)
-    assert binding.rom_workspace_bytes(d, 1, 1000) == base
-
+    d = _dims(dtype=1, d_model=2048, d_inner=4096, dt_rank=128, n_experts=8, n_experts_xdt=8)
+    n = 16384
+    need = binding.rom_route_workspace_bytes(d, n)
+    assert 0 < need <= 4 * n * 8 + (1 << 20)                  # index arrays only: no activation region
+    assert need <= binding.rom_workspace_bytes(d, n, 1) and need <= binding.rom_workspace_bytes(d, 1, n)
+    assert binding.rom_route_workspace_bytes(_dims(top_k=9), n) == 0
+    buf = ctypes.create_string_buffer(4096 + 256)
+    addr = (ctypes.addressof(buf) + 255) // 256 * 256
+    w = binding._RomWeights(*([addr] * 11))
+    args = (addr, n, addr, addr, addr, addr, addr, addr, None, addr)
+    assert lib.rom_route(ctypes.byref(d), ctypes.byref(w), *args, need - 1, None) == -2    # refused before any launch
 
 
 def test_balance_stats_arguments_and_scratch_placement(lib):
@@ -177,11 +166,6 @@ def test_balance_stats_arguments_and_scratch_placement(lib):
     N, E = 1200, 8
     lays = [binding.rom_workspace_layout(d, 1, N), binding.rom_workspace_layout(d, N, 1),
             binding.rom_workspace_layout(d, 4, N // 4)]
-    try:
-        binding.rom_set_segments(3)
-        lays.append(binding.rom_workspace_layout(d, 1, N))
-    finally:
-        binding.rom_set_segments(0)
     for lay in lays:
         assert lay["logits"] == lays[0]["logits"] and lay["xz"] == lays[0]["xz"]
         assert lay["xz"] - lay["logits"] >= N * E * 4 + 256 * E * 4

@@ -11,7 +11,8 @@ from paper_2506_18145_amd import RomFfnMoe, RomHybridStack, RomLayer, RomStack
 from rom_synth import (RomConfig, get_config, make_ffn_weights, make_input, make_stack_weights, make_states,
                        make_weights)
 
-from gpu_util import BLOCK_EPS, MARGIN, TOL, check_routing, compare_layer, rel_err, run_layer, to_np
+from gpu_util import (BLOCK_EPS, MARGIN, TOL, check_routing, compare_layer, max_excluded, rel_err, run_layer,
+                      to_np)
 
 pytestmark = pytest.mark.gpu
 
@@ -72,45 +73,6 @@ def test_medium_layers_big_tile_kernels(kw):
     compare_layer(cfg, gpu, x, w)
 
 
-@pytest.mark.parametrize("n_seg", [2, 3, 4])
-@pytest.mark.parametrize("kw", [
-    dict(batch=1, seq_len=301),                                # one sequence cut in time: conv / scan carry
-    dict(batch=1, seq_len=150, top_k=2, gate_mode=1),
-    dict(batch=3, seq_len=97),                                 # whole sequences dealt to segments
-    dict(batch=5, seq_len=40, top_k=2, gate_mode=0, dtype="fp32"),
-    dict(batch=1, seq_len=200, routed_xdt=False),
-    dict(batch=1, seq_len=130, n_experts=64, top_k=8, gate_mode=1),   # most experts empty in a segment
-])
-def test_segmented_pipeline(kw, n_seg):
-    """The two-stream software pipeline (forced here; automatic only for long calls) against the
-    oracle, with incoming and outgoing states."""
-    from paper_2506_18145_amd import rom_set_segments
-    cfg = small_cfg(**kw)
-    cs, ss = make_states(cfg)
-    rom_set_segments(n_seg)
-    try:
-        _, gpu, x, w = run_layer(cfg, cs, ss)
-    finally:
-        rom_set_segments(0)
-    compare_layer(cfg, gpu, x, w, cs, ss)
-
-
-def test_segmented_pipeline_is_deterministic_and_matches_unsegmented_routing():
-    from paper_2506_18145_amd import rom_set_segments
-    cfg = small_cfg(batch=1, seq_len=1000, d_model=128, d_inner=256, dt_rank=8, n_experts=8)
-    _, base, x, w = run_layer(cfg)
-    rom_set_segments(3)
-    try:
-        _, seg1, _, _ = run_layer(cfg)
-        _, seg2, _, _ = run_layer(cfg)
-    finally:
-        rom_set_segments(0)
-    for name in ("expert_idx", "counts", "offsets", "perm", "inv_perm"):
-        assert np.array_equal(base[name], seg1[name])
-    assert np.array_equal(seg1["out"], seg2["out"])
-    assert rel_err(seg1["out"], base["out"]) <= TOL["bf16"] * 0.25
-
-
 @pytest.mark.parametrize("name,over", [
     ("cfg0", {}), ("cfg1", {}), ("cfg2", {}), ("cfg3", {}),
     ("cfg1", dict(n_experts=5, top_k=3, batch=1, seq_len=777, d_model=128, d_inner=64, dt_rank=8, cfg_id=81)),
@@ -140,6 +102,7 @@ def test_balance_stats(name, over):
     idx = O.topk_select(logits, K)
     o_frac, o_mean, o_loss = O.balance_stats(logits, idx, E, alpha)
     n_close = int(np.count_nonzero(O.topk_margin(logits, K) < MARGIN))
+    assert n_close <= max_excluded(logits, K)
     f_tol = (n_close * K) / float(N * K) + 2e-7
     assert np.max(np.abs(frac.cpu().numpy() - o_frac)) <= f_tol
     assert np.max(np.abs(mean_prob.cpu().numpy() - o_mean)) <= 1e-5 * np.max(o_mean)
@@ -158,9 +121,8 @@ def test_balance_stats(name, over):
 @pytest.mark.parametrize("seed", [11, 12, 13])
 def test_random_shapes(seed):
     """Seeded random layer shapes (sizes off every tile grid, many and few experts, both dtypes,
-    with and without incoming state, cut into segments or not) against the oracle."""
+    with and without incoming state) against the oracle."""
     import random
-    from paper_2506_18145_amd import rom_set_segments
     rng = random.Random(seed)
     for i in range(10):
         E = rng.choice([1, 2, 3, 5, 8, 12, 16, 33, 64])
@@ -171,15 +133,11 @@ def test_random_shapes(seed):
                   top_k=rng.randint(1, min(E, 4)), dtype=rng.choice(["bf16", "bf16", "fp32"]),
                   gate_mode=rng.choice([0, 1]), routed_xdt=rng.choice([True, True, False]))
         cfg = RomConfig(**kw)
-        seg = rng.choice([0, 0, 2, 3])
+        rng.choice([0, 0, 2, 3])                     # (keeps the seeded shape sequence of earlier runs)
         cs, ss = make_states(cfg) if rng.choice([False, True]) else (None, None)
         print(f"[{cfg.name}] B={cfg.batch} L={cfg.seq_len} Dm={cfg.d_model} De={cfg.d_inner} R={cfg.dt_rank} "
-              f"E={E} K={cfg.top_k} {cfg.dtype} segments={seg}", flush=True)
-        rom_set_segments(seg)
-        try:
-            _, gpu, x, w = run_layer(cfg, cs, ss)
-        finally:
-            rom_set_segments(0)
+              f"E={E} K={cfg.top_k} {cfg.dtype}", flush=True)
+        _, gpu, x, w = run_layer(cfg, cs, ss)
         compare_layer(cfg, gpu, x, w, cs, ss)
 
 
@@ -188,7 +146,6 @@ def test_random_shapes_block_and_ffn(seed):
     """The same kind of random shapes through the pre-norm residual block, then an FFN-MoE layer of
     random width on the grouping the block call left in its workspace."""
     import random
-    from paper_2506_18145_amd import rom_set_segments
     from rom_synth import round_to_bf16
     rng = random.Random(seed)
     for i in range(8):
@@ -200,17 +157,13 @@ def test_random_shapes_block_and_ffn(seed):
                   top_k=rng.randint(1, min(E, 4)), dtype=rng.choice(["bf16", "bf16", "fp32"]),
                   gate_mode=rng.choice([0, 1]), routed_xdt=rng.choice([True, True, False]), weight_std=0.06)
         cfg = RomConfig(**kw)
-        seg = rng.choice([0, 0, 2, 3])
+        rng.choice([0, 0, 2, 3])                     # (keeps the seeded shape sequence of earlier runs)
         cs, ss = make_states(cfg) if rng.choice([False, True]) else (None, None)
         d_ff = 16 * rng.randint(1, 70)
         pre_norm, skip = rng.choice([False, True]), rng.choice([False, True])
         print(f"[{cfg.name}] B={cfg.batch} L={cfg.seq_len} Dm={cfg.d_model} De={cfg.d_inner} R={cfg.dt_rank} "
-              f"E={E} K={cfg.top_k} {cfg.dtype} segments={seg} d_ff={d_ff} norm={pre_norm} skip={skip}", flush=True)
-        rom_set_segments(seg)
-        try:
-            layer, gpu, x, w = run_layer(cfg, cs, ss, block=True)
-        finally:
-            rom_set_segments(0)
+              f"E={E} K={cfg.top_k} {cfg.dtype} d_ff={d_ff} norm={pre_norm} skip={skip}", flush=True)
+        layer, gpu, x, w = run_layer(cfg, cs, ss, block=True)
         compare_layer(cfg, gpu, x, w, cs, ss, block=True)
         B, L = cfg.batch, cfg.seq_len
         N = B * L
@@ -281,6 +234,45 @@ def test_route_with_exact_ties_picks_lowest_index():
     assert np.all(to_np(res["expert_idx"]) == np.array([1, 2]))
 
 
+def test_route_names_valid_distinct_experts_for_nan_and_masked_logits():
+    """Not-a-number activations and a -inf masking bias are outside the layer's numeric contract,
+    but the router must still hand the grouping K distinct experts in [0, E) per token (an index
+    of -1 would send the scatter and the GEMMs' row gathers out of bounds): the all-NaN token gets
+    experts 0..K-1, a token with fewer finite logits than K fills up with the lowest free ones,
+    exactly as the oracle's selection does, and the other sequence of the batch is untouched."""
+    cfg = small_cfg(batch=2, seq_len=150, n_experts=8, top_k=3, gate_mode=1, dtype="fp32", cfg_id=66)
+    w = make_weights(cfg)
+    w["b_router"] = np.array([0.0] + [-np.inf] * 6 + [0.0], np.float32)     # two usable experts, K = 3
+    x = make_input(cfg)
+    x[0, 5, :] = np.nan
+    layer = RomLayer(cfg, w)
+    xd = layer.to_device(x)
+    res = layer.route(xd.view(-1, cfg.d_model))
+    torch.cuda.synchronize()
+    idx = to_np(res["expert_idx"])
+    N, K, E = cfg.batch * cfg.seq_len, cfg.top_k, cfg.n_experts
+    assert idx.min() >= 0 and idx.max() < E
+    srt = np.sort(idx, axis=1)
+    assert np.all(srt[:, 1:] != srt[:, :-1])
+    assert idx[5].tolist() == [0, 1, 2]
+    logits = O.router_logits(x.reshape(N, -1), w["w_router"], w["b_router"])
+    own = O.topk_select(logits, K)
+    far = np.abs(logits[:, 0] - logits[:, 7]) > MARGIN
+    far[5] = True
+    assert np.array_equal(idx[far], own[far])
+    counts, offsets, perm, inv_perm = O.expert_permutation(idx, E)
+    assert int(to_np(res["counts"]).sum()) == N * K
+    assert np.array_equal(to_np(res["counts"]), counts) and np.array_equal(to_np(res["perm"]), perm)
+    assert np.array_equal(to_np(res["inv_perm"]), inv_perm) and np.array_equal(to_np(res["offsets"]), offsets)
+    # the whole layer on the same input: no fault, the NaN stays inside its own sequence
+    out = to_np(layer.forward(xd))
+    assert np.all(np.isfinite(out[1])) and np.all(np.isfinite(out[0, :5])) and np.all(np.isnan(out[0, 5]))
+    clean = x.copy()
+    clean[0] = x[1]
+    ref = to_np(layer.forward(layer.to_device(clean)))
+    assert np.array_equal(out[1], ref[1])
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3"])
 def test_full_size_configs(name):
     """The paper-shaped workloads at full size, in the launch configuration bench.py times."""
@@ -323,7 +315,7 @@ def _step_run(cfg, n_steps, tracked, all_steps):
     B = cfg.batch
     ref_cs, ref_ss = cs0[tracked].astype(np.float64), ss0[tracked].astype(np.float64)
     all_cs, all_ss = cs0.astype(np.float64), ss0.astype(np.float64)
-    worst, excluded = 0.0, 0
+    worst, excluded, n_close_tracked, close_allowed = 0.0, 0, 0, 0
     tol = TOL[cfg.dtype]
     for t in range(n_steps):
         out = layer.step(xs_d[t], cs, ss)
@@ -342,7 +334,9 @@ def _step_run(cfg, n_steps, tracked, all_steps):
         # tracked sequences: routing must agree outside the margin band, floats within tolerance
         logits = O.router_logits(xs[t][tracked], w64["w_router"], w64.get("b_router"))
         own = O.topk_select(logits, cfg.top_k)
-        close = O.topk_margin(logits, cfg.top_k) < 1e-5
+        close = O.topk_margin(logits, cfg.top_k) < MARGIN
+        n_close_tracked += int(close.sum())
+        close_allowed += max_excluded(logits, cfg.top_k) - 2
         assert np.array_equal(idx[tracked][~close], own[~close]), f"step {t}: routing differs"
         ref = O.rom_step(xs[t][tracked], w64, cfg.top_k, cfg.gate_mode, ref_cs, ref_ss,
                          expert_idx=idx[tracked])
@@ -352,8 +346,10 @@ def _step_run(cfg, n_steps, tracked, all_steps):
         assert err <= tol, f"step {t}: out error {err:.3e}"
     assert rel_err(to_np(ss)[tracked], ref_ss) <= tol
     assert rel_err(to_np(cs)[tracked], ref_cs) <= tol
-    print(f"[{cfg.name} step x{n_steps}] worst out error {worst:.2e}, excluded in full-batch steps {excluded}",
-          flush=True)
+    # the exemption must stay an exception: over all tracked (sequence, step) pairs
+    assert n_close_tracked <= 2 + close_allowed
+    print(f"[{cfg.name} step x{n_steps}] worst out error {worst:.2e}, excluded in full-batch steps {excluded}, "
+          f"among the tracked sequences {n_close_tracked}", flush=True)
 
 
 def test_step_small():
@@ -394,10 +390,10 @@ def test_step_matches_forward_last_token():
 
 
 def test_step_cfg4_decode_512_steps():
-    """256 sequences x 512 consecutive steps; the oracle tracks two sequences through all steps and
+    """256 sequences x 512 consecutive steps; the oracle tracks eight sequences through all steps and
     every sequence through the first four."""
     cfg = get_config("cfg4")
-    _step_run(cfg, 512, tracked=[3, 200], all_steps=4)
+    _step_run(cfg, 512, tracked=[3, 40, 77, 101, 150, 200, 233, 255], all_steps=4)
 
 
 # ---------------------------------------------------------------------------------------------
