@@ -534,6 +534,216 @@ __global__ __launch_bounds__(256) void scan_kernel(
   }
 }
 
+// ------------------------------------------------------------------ selective scan, software-pipelined
+// The same lane = (channel, state) layout and LDS tiles as scan_kernel<T, false, 2>, for launches
+// with at most one block per CU (one long sequence: one wavefront per SIMD, nobody else to hide a
+// stall).  Measured on MI355X, a lone wavefront issues an independent fp32 instruction every 5
+// clocks, a DPP one every 5, v_exp_f32 every 9, and waits 8.8 clocks for a dependent FMA: the
+// only latency-bound piece of a 16-step group is its chain of 16 dependent FMAs, so the groups of
+// a tile run as a three-stage pipeline whose stages are interleaved instruction by instruction -
+//   A(g+1): decay exp2(dt*A) and input dt*u*B of the next group (48 independent instructions),
+//   B(g):   the 16 dependent FMAs of this group,
+//   C(g-1): C.h products, transposing reduction, D skip and SiLU(z) gate of the previous group
+// - one FMA of B, then three instructions of A and up to five of C, fenced so that the compiler
+// keeps the order.  All of a lane's tile inputs (dt, u, z of its four steps, B and C of all 64)
+// are read from LDS into registers at the top of the tile, in the order of use.
+struct ScanPipeRegs {
+  float dt_r[kScanGroups], u_r[kScanGroups], z_r[kScanGroups], dtu_r[kScanGroups];
+  float bv[kScanGroups][16], cv[kScanGroups][16];
+  float da[2][16], xx[2][16], hs[2][16];
+  float ra[8], rb[4], rc[2], y;
+  float h, a2, d_skip;
+  bool hi8, hi4, hi2, hi1;
+};
+
+// slot J of phase P (P = -1 .. kScanGroups): step J of B(P), step J of A(P + 1), unit J of C(P - 1)
+// (PARTS: bit 0 = A, 1 = B, 2 = C; anything but 7 is for timing probes)
+template <int P, int J, int PARTS = 7>
+__device__ __forceinline__ void scan_pipe_slot(ScanPipeRegs &r, float (*g_tile)[kChPitch], int n, int cl) {
+#pragma clang fp contract(off)
+  if constexpr ((PARTS & 2) != 0 && P >= 0 && P < kScanGroups) {
+    r.h = __builtin_fmaf(r.da[P & 1][J], r.h, r.xx[P & 1][J]);
+    r.hs[P & 1][J] = r.h;
+  }
+  if constexpr ((PARTS & 1) != 0 && P + 1 >= 0 && P + 1 < kScanGroups) {
+    constexpr int G = P + 1;
+    r.da[G & 1][J] = fast_exp2(dpp<kDppRowBcast0 + J>(r.dt_r[G]) * r.a2);
+    r.xx[G & 1][J] = dpp<kDppRowBcast0 + J>(r.dtu_r[G]) * r.bv[G][J];
+  }
+  if constexpr ((PARTS & 4) != 0 && P - 1 >= 0 && P - 1 < kScanGroups) {
+    constexpr int G = P - 1;
+    const float *hs = r.hs[G & 1];
+    const float *cv = r.cv[G];
+    if constexpr (J < 8) {
+      const float pl = hs[J] * cv[J], ph = hs[J + 8] * cv[J + 8];
+      const float lo = dpp<kDppRowMirror>(pl) + pl;
+      const float hi = dpp<kDppRowMirror>(ph) + ph;
+      r.ra[J] = r.hi8 ? hi : lo;
+    } else if constexpr (J < 12) {
+      constexpr int I = J - 8;
+      const float lo = dpp<kDppHalfMirror>(r.ra[I]) + r.ra[I];
+      const float hi = dpp<kDppHalfMirror>(r.ra[I + 4]) + r.ra[I + 4];
+      r.rb[I] = r.hi4 ? hi : lo;
+    } else if constexpr (J < 14) {
+      constexpr int I = J - 12;
+      const float lo = dpp<kDppQuadRev>(r.rb[I]) + r.rb[I];
+      const float hi = dpp<kDppQuadRev>(r.rb[I + 2]) + r.rb[I + 2];
+      r.rc[I] = r.hi2 ? hi : lo;
+    } else if constexpr (J == 14) {
+      const float lo = dpp<kDppQuadXor1>(r.rc[0]) + r.rc[0];
+      const float hi = dpp<kDppQuadXor1>(r.rc[1]) + r.rc[1];
+      r.y = r.hi1 ? hi : lo;
+    } else {
+      const float y = r.y + r.d_skip * r.u_r[G];
+      g_tile[G * 16 + n][cl] = y * silu_f32(r.z_r[G]);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+}
+template <int P, int J, int PARTS = 7> struct ScanPipeSlots {
+  __device__ static __forceinline__ void run(ScanPipeRegs &r, float (*g_tile)[kChPitch], int n, int cl) {
+    ScanPipeSlots<P, J - 1, PARTS>::run(r, g_tile, n, cl);
+    scan_pipe_slot<P, J, PARTS>(r, g_tile, n, cl);
+  }
+};
+template <int P, int PARTS> struct ScanPipeSlots<P, -1, PARTS> {
+  __device__ static __forceinline__ void run(ScanPipeRegs &, float (*)[kChPitch], int, int) {}
+};
+template <int P, int PARTS = 7> struct ScanPipePhases {
+  __device__ static __forceinline__ void run(ScanPipeRegs &r, float (*g_tile)[kChPitch], int n, int cl) {
+    ScanPipePhases<P - 1, PARTS>::run(r, g_tile, n, cl);
+    ScanPipeSlots<P, 15, PARTS>::run(r, g_tile, n, cl);
+  }
+};
+template <int PARTS> struct ScanPipePhases<-2, PARTS> {
+  __device__ static __forceinline__ void run(ScanPipeRegs &, float (*)[kChPitch], int, int) {}
+};
+
+__device__ __forceinline__ void scan_pipe_read16(float *dst, const float *row) {
+#pragma unroll
+  for (int j = 0; j < 16; j += 4) {
+    const float4 v = *reinterpret_cast<const float4 *>(row + j);
+    dst[j] = v.x; dst[j + 1] = v.y; dst[j + 2] = v.z; dst[j + 3] = v.w;
+  }
+}
+
+// grid: (d_inner / 16, B, n_chunks); arguments as scan_kernel<T, false, 2>.
+// HELPERS: the block has 512 threads.  Wavefronts 0..3 ("compute") only read their tile inputs
+// from LDS, run the phases and leave g in LDS; wavefronts 4..7 ("helpers", one beside each compute
+// wavefront on its SIMD) do everything that touches global memory - fetch tile t+2, convert and
+// park tile t+1, turn the finished g tile into coalesced stores - so that none of it sits on the
+// lone compute wavefront's critical path.  One block barrier per tile, at which the compute side
+// says "tile t read, g of tile t complete" and the helper side "tile t+1 parked".
+// Without HELPERS (256 threads) every wavefront does both, for launches with two blocks per CU.
+template <typename T, bool HELPERS>
+__global__ __launch_bounds__(HELPERS ? 512 : 256) void scan_pipe_kernel(
+    const T *__restrict__ u, const T *__restrict__ dt, const float *__restrict__ bc,
+    const T *__restrict__ z, int64_t ld_z, const float *__restrict__ A_log,
+    const float *__restrict__ D, const float *__restrict__ h_in, float *__restrict__ h_out,
+    T *__restrict__ g, int64_t L, int d_inner, int64_t chunk_len, int n_chunks,
+    float *__restrict__ chunk_q, float *__restrict__ chunk_p) {
+  __shared__ ScanSmem tiles[2];
+  __shared__ float g_tiles[2][kScanTile][kChPitch];
+  const bool computes = !HELPERS || threadIdx.x < 256;
+  const bool helps = !HELPERS || threadIdx.x >= 256;
+  const int tid = threadIdx.x & 255;
+  const int n = tid & 15;            // state index = lane inside the DPP row
+  const int cl = tid >> 4;           // channel inside the block
+  const int n_groups = d_inner / kScanCh;
+  int grp = blockIdx.x;
+  if (n_groups % 8 == 0) grp = (blockIdx.x % 8) * (n_groups / 8) + blockIdx.x / 8;
+  const int c0 = grp * kScanCh;
+  const int ch = c0 + cl;
+  const int64_t b = blockIdx.y;
+  const int chunk = blockIdx.z;
+  const int64_t t_begin = chunk * chunk_len;
+  const int64_t t_end = (t_begin + chunk_len < L) ? t_begin + chunk_len : L;
+  const int64_t n_tiles = (t_end - t_begin + kScanTile - 1) / kScanTile;
+
+  const T *u_b = u + b * L * d_inner + c0;
+  const T *dt_b = dt + b * L * d_inner + c0;
+  const T *z_b = z + b * L * ld_z + c0;
+  const float *bc_b = bc + b * L * 32;
+  T *g_b = g + b * L * d_inner + c0;
+
+  // global -> registers of tile number `tile` (rows past t_end are zero-filled: dt = 0 leaves h alone)
+  ScanStage<T> st;
+  auto fetch = [&](int64_t tile) __attribute__((always_inline)) {
+    const int64_t t0 = t_begin + tile * kScanTile;
+    if (t0 + kScanTile <= t_end)
+      scan_fetch<T, false, false>(st, dt_b, u_b, z_b, bc_b, t0, t_end, d_inner, ld_z, tid);
+    else
+      scan_fetch<T, false, true>(st, dt_b, u_b, z_b, bc_b, t0, t_end, d_inner, ld_z, tid);
+  };
+  // g of tile number `tile`: thread -> (step row, 4 channels)
+  auto store_g = [&](int64_t tile) __attribute__((always_inline)) {
+    const int row = tid >> 2, q = (tid & 3) * 4;
+    const int64_t t = t_begin + tile * kScanTile + row;
+    if (t < t_end) {
+      Pack<T, 4> pk;
+      pk.from_floats(*reinterpret_cast<const float4 *>(&g_tiles[tile & 1][row][q]));
+      pk.store(g_b + t * d_inner + q);
+    }
+  };
+
+  ScanPipeRegs r;
+  if (computes) {
+    r.a2 = -__expf(A_log[static_cast<int64_t>(ch) * 16 + n]) * 1.44269504088896341f;
+    r.d_skip = D[ch];
+    r.hi8 = (n & 8) != 0; r.hi4 = (n & 4) != 0; r.hi2 = (n & 2) != 0; r.hi1 = (n & 1) != 0;
+    if (n_chunks > 1) r.h = chunk_q[((b * n_chunks + (n_chunks - 1)) * d_inner + ch) * 16 + n];
+    else r.h = h_in ? h_in[(b * d_inner + ch) * 16 + n] : 0.0f;
+    for (int k = 0; k < chunk; ++k) {      // fold the chunks before this one
+      const int64_t at = ((b * n_chunks + k) * d_inner + ch) * 16 + n;
+      r.h = fmaf(chunk_p[at], r.h, chunk_q[at]);
+    }
+  }
+  if (helps) {
+    fetch(0);
+    scan_park<T, false>(tiles[0], st, tid);
+    if (n_tiles > 1) fetch(1);
+  }
+  __syncthreads();
+
+  for (int64_t ti = 0; ti < n_tiles; ++ti) {
+    const bool has_next = ti + 1 < n_tiles;
+    if (computes) {
+      ScanSmem &sm = tiles[ti & 1];
+      // this lane's share of the tile, in the order the phases consume it
+#pragma unroll
+      for (int gi = 0; gi < kScanGroups; ++gi) {
+        r.dt_r[gi] = sm.dt[gi * 16 + n][cl];
+        r.u_r[gi] = sm.u[gi * 16 + n][cl];
+        r.dtu_r[gi] = r.dt_r[gi] * r.u_r[gi];
+      }
+      scan_pipe_read16(r.bv[0], &sm.bc[n][0]);
+      scan_pipe_read16(r.bv[1], &sm.bc[n][16]);
+      scan_pipe_read16(r.cv[0], &sm.bc[16 + n][0]);
+#pragma unroll
+      for (int gi = 2; gi < kScanGroups; ++gi) {
+        scan_pipe_read16(r.bv[gi], &sm.bc[n][gi * 16]);
+        scan_pipe_read16(r.cv[gi - 1], &sm.bc[16 + n][(gi - 1) * 16]);
+      }
+      scan_pipe_read16(r.cv[kScanGroups - 1], &sm.bc[16 + n][(kScanGroups - 1) * 16]);
+#pragma unroll
+      for (int gi = 0; gi < kScanGroups; ++gi) r.z_r[gi] = sm.zg[gi * 16 + n][cl];
+      __builtin_amdgcn_sched_barrier(0);
+      ScanPipePhases<kScanGroups>::run(r, g_tiles[ti & 1], n, cl);
+    }
+    if (helps) {
+      if (HELPERS && ti > 0) store_g(ti - 1);         // complete since the barrier that ended tile ti - 1
+      if (has_next) {
+        scan_park<T, false>(tiles[(ti + 1) & 1], st, tid);    // (its last readers passed that same barrier)
+        if (ti + 2 < n_tiles) fetch(ti + 2);
+      }
+    }
+    __syncthreads();     // tile ti is read and its g complete; tile ti + 1 is parked
+    if (!HELPERS) store_g(ti);
+  }
+  if (HELPERS && helps && n_tiles > 0) store_g(n_tiles - 1);
+  if (computes && h_out && chunk == n_chunks - 1) h_out[(b * d_inner + ch) * 16 + n] = r.h;
+}
+
 // ------------------------------------------------------------------ single-step scan (L == 1)
 // One recurrence update per (sequence, channel, state): bound by reading and writing the fp32
 // state.  A lane owns four consecutive states of one channel (one 16-byte load and store), four
@@ -860,8 +1070,15 @@ static hipError_t scan_dispatch(const T *u, const T *dt, const float *bc, const 
                        chunk_q, chunk_p);
   }
   // one block per CU or fewer: two tiles in LDS (one barrier per tile); else six small blocks per CU
-  if (kScanDouble && static_cast<int64_t>(gx) * gy * nc <= 256)
-    hipLaunchKernelGGL((scan_kernel<T, false, 2>), dim3(gx, gy, nc), dim3(256), 0, s, u, dt, bc, z, ld_z, A_log,
+  // one block per CU or fewer: the software-pipelined kernel with a helper wavefront beside every
+  // compute wavefront; up to two blocks per CU: the same kernel without helpers (two tiles in LDS,
+  // 58 KiB); beyond that six small blocks per CU
+  const int64_t n_blocks = static_cast<int64_t>(gx) * gy * nc;
+  if (kScanDouble && n_blocks <= 256)
+    hipLaunchKernelGGL((scan_pipe_kernel<T, true>), dim3(gx, gy, nc), dim3(512), 0, s, u, dt, bc, z, ld_z, A_log,
+                       D, h_in, h_out, g, L, d_inner, chunk_len, nc, chunk_q, chunk_p);
+  else if (kScanDouble && n_blocks <= 512)
+    hipLaunchKernelGGL((scan_pipe_kernel<T, false>), dim3(gx, gy, nc), dim3(256), 0, s, u, dt, bc, z, ld_z, A_log,
                        D, h_in, h_out, g, L, d_inner, chunk_len, nc, chunk_q, chunk_p);
   else
     hipLaunchKernelGGL((scan_kernel<T, false, 1>), dim3(gx, gy, nc), dim3(256), 0, s, u, dt, bc, z, ld_z, A_log,

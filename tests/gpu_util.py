@@ -18,7 +18,17 @@ MARGIN = 1e-5     # tokens whose top-K logit margin is below this are excluded f
 # meaning at zero crossings).  An element of typical size carries the same rounding error as the
 # tensor maximum does relative to itself, but the errors of the bf16 intermediates it was computed
 # from scale with *their* typical size, so the ratio is a few times the normalised figure: the
-# bound is 2.5 x TOL, and the measured value is printed next to it.
+# bound is 2.5 x TOL.  It is asserted for xz, u, dt_low, B/C and dt, whose elements all live on
+# the scale of their tensor.  g and out are heavy-tailed (y = C.h cancels, and h spans decades
+# across channels and tokens): an element whose terms are as large as the tensor's largest but
+# cancel carries the largest elements' absolute error against a small value, so there the figure
+# is printed only.  What is asserted for them (same bound) is the componentwise form of the
+# textbook error bound of a sum, |error of sum| <= eps * sum |terms|: the oracle is run once more
+# on absolute values (|u|, |B|, |C|, |D|, |h0| through the scan, then |SiLU(z)| and |W_out|; the
+# inputs that are projection or conv outputs, whose own error is uniform over their tensor, enter
+# at |value| + rms), which gives every element the size of the terms it was added up from - it
+# follows dt, the channel and the history of the state, which is where the decades come from -
+# and the error of every element of g and out is held to the tolerance at that scale.
 ELEM_TOL = {"fp32": 2.5e-4, "bf16": 5e-2}
 
 
@@ -46,6 +56,36 @@ def col_err(got, ref) -> float:
     scale = np.max(np.abs(ref), axis=0)
     scale = np.where(scale > 0, scale, 1.0)
     return float(np.max(np.max(np.abs(got - ref), axis=0) / scale))
+
+
+def term_scales(cfg, ref, w_np, idx, ssm_state):
+    """Size of the terms every element of g and of the layer output is summed from: the oracle's
+    scan, gate and out projection evaluated on absolute values (of the oracle's own u, dt, B, C, z
+    and gate).  Returns (g_abs [N, D_e], out_abs [N, D_m])."""
+    n_tok, d_e = ref["u"].shape
+    bsz = cfg.batch
+    length = n_tok // bsz
+    r, d_s = cfg.dt_rank, cfg.d_state
+    # u, B, C and z are themselves sums that cancel (conv taps, projections), with an error that is
+    # uniform over their tensor: each enters at |value| + rms of its tensor
+    rms = lambda v: np.sqrt(np.mean(np.square(v)))
+    bm, cm = ref["xdbl"][:, r:r + d_s], ref["xdbl"][:, r + d_s:]
+    b_abs = (np.abs(bm) + rms(bm)).reshape(bsz, length, d_s)
+    c_abs = (np.abs(cm) + rms(cm)).reshape(bsz, length, d_s)
+    u_abs = (np.abs(ref["u"]) + rms(ref["u"])).reshape(bsz, length, d_e)
+    a = -np.exp(np.asarray(w_np["A_log"], np.float64))
+    y_abs, _ = O.selective_scan(u_abs, ref["dt"].reshape(bsz, length, d_e), b_abs, c_abs, a,
+                                np.abs(np.asarray(w_np["D"], np.float64)),
+                                None if ssm_state is None else np.abs(np.asarray(ssm_state, np.float64)))
+    # the gate factor SiLU(z): z is a projection output whose error is uniform over the tensor
+    # (every element sums terms of one size), so its factor is floored at the tensor's rms
+    z = ref["xz"][:, d_e:]
+    g_abs = y_abs.reshape(n_tok, d_e) * (np.abs(O.silu(z)) + np.sqrt(np.mean(z * z)))
+    w_out_abs = np.abs(np.asarray(w_np["w_out"], np.float64))
+    out_abs = np.zeros((n_tok, cfg.d_model))
+    for k in range(cfg.top_k):
+        out_abs += ref["gate"][:, k:k + 1] * O.routed_linear(g_abs, w_out_abs, idx[:, k:k + 1])
+    return g_abs, out_abs
 
 
 def max_excluded(logits, top_k: int) -> int:
@@ -142,7 +182,7 @@ def compare_layer(cfg, gpu, x_np, w_np, conv_state=None, ssm_state=None, stages=
     else:
         ref = O.rom_layer_forward(x_np, w_np, cfg.top_k, cfg.gate_mode, conv_state, ssm_state, expert_idx=idx)
     tol = TOL[cfg.dtype]
-    errs, elem = {}, {}
+    errs, elem, scaled = {}, {}, {}
     if stages:
         r = cfg.dt_rank
         pairs = {"xz": (gpu["xz"], ref["xz"]), "u": (gpu["u"], ref["u"]),
@@ -154,6 +194,13 @@ def compare_layer(cfg, gpu, x_np, w_np, conv_state=None, ssm_state=None, stages=
         errs["dt/col"] = col_err(gpu["dt"], ref["dt"])       # every channel's dt at its own scale
     errs["out"] = rel_err(gpu["out"], ref["out"])
     elem["out"] = elem_err(gpu["out"], ref["out"])
+    if stages:
+        g_abs, out_abs = term_scales(cfg, ref, w_np, idx, ssm_state)
+        scaled["g"] = float(np.max(np.abs(np.asarray(gpu["g"], np.float64) - ref["g"]) / (g_abs + 1e-300)))
+        got_out = np.asarray(gpu["out"], np.float64).reshape(out_abs.shape)
+        if block:            # the skip term is exact up to the output's own rounding
+            out_abs = out_abs + np.abs(np.asarray(x_np, np.float64)).reshape(out_abs.shape)
+        scaled["out"] = float(np.max(np.abs(got_out - ref["out"].reshape(out_abs.shape)) / (out_abs + 1e-300)))
     if block:
         # the branch alone, so that an error in it cannot hide behind a large skip term; the
         # output's own rounding (unit roundoff of the activation type: 8 significant bits in
@@ -166,9 +213,13 @@ def compare_layer(cfg, gpu, x_np, w_np, conv_state=None, ssm_state=None, stages=
     errs["conv_state"] = rel_err(gpu["conv_state"], ref["conv_state"])
     print(f"[{cfg.name}] excluded={n_excl} counts={gpu['counts'].tolist()} "
           + " ".join(f"{k}={v:.2e}" for k, v in errs.items())
-          + " | per element (rms floor): " + " ".join(f"{k}={v:.2e}" for k, v in elem.items()), flush=True)
+          + " | per element (rms floor): " + " ".join(f"{k}={v:.2e}" for k, v in elem.items())
+          + " | at the scale of the summed terms: " + " ".join(f"{k}={v:.2e}" for k, v in scaled.items()), flush=True)
     bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, f"beyond tolerance {tol}: {bad}"
-    bad = {k: v for k, v in elem.items() if not v <= ELEM_TOL[cfg.dtype]}
-    assert not bad, f"per-element error beyond {ELEM_TOL[cfg.dtype]}: {bad}"
+    etol = ELEM_TOL[cfg.dtype]
+    bad = {k: v for k, v in elem.items() if k not in ("g", "out") and not v <= etol}
+    assert not bad, f"per-element error beyond {etol}: {bad}"
+    bad = {k: v for k, v in scaled.items() if not v <= etol}
+    assert not bad, f"error beyond {etol} of the summed terms' size: {bad}"
     return ref, errs
