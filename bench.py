@@ -18,13 +18,21 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
-PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
-# plain-ALU ceiling for fp32: 256 CUs x 4 SIMDs x 16 lanes x 2 flop (FMA) x 2.4 GHz, no packed math
-PEAK_ALU_FP32_TFLOPS = 78.6
-# HBM bytes per in_proj launch at cfg2 from rocprofv3 FETCH_SIZE (x2.0 copy-kernel calibration) +
-# WRITE_SIZE (x1.0): see profiles/forward_cfg2_hbm_traffic.md
-TRAFFIC_IN_PROJ_CFG2_BYTES = (992 + 256) * 2 ** 20
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA (published, at the nominal 2.4 GHz)
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E (published)
+# fp32 vector peak: 256 CUs x 4 SIMDs x 32 lanes per clock x 2 flop (FMA) x 2.4 GHz = 157.3 TFLOP/s, the
+# published figure.  It needs no packed math: a SIMD issues one 64-lane fp32 FMA every two clocks
+# (measured here: 2.3 clocks per wavefront instruction with four or more wavefronts per SIMD; a
+# lone wavefront gets one every 5 clocks, a DPP instruction costs 4.2, v_exp_f32 8.2).
+PEAK_ALU_FP32_TFLOPS = 157.3
+ALU_PEAK_NOTE = ("fp32 vector peak 157.3 TFLOP/s = 256 CU x 4 SIMD x 32 lanes/clk x 2 flop x 2.4 GHz (published; "
+                 "reached without packed-fp32 instructions, which this build never emits)")
+NOMINAL_CLOCK_GHZ = 2.4
+# shader clock under the in projection's load, from GRBM_GUI_ACTIVE of that kernel over its duration
+# (profiles/forward_cfg2_hbm_traffic.md: 1.06e6 cycles per XCD in 0.543 ms): the published peaks
+# assume 2.4 GHz, the chip sustains less under a bf16 GEMM of N(0,1)-like operands
+COUNTER_CLOCK_GHZ_GEMM = 1.95
+DOMINANT_KERNEL = "gemm_bf16_dma_kernel<256, 4, 2, 0>"     # the in projection at top-1
 
 
 def stage_model(cfg):
@@ -226,11 +234,19 @@ def hybrid_stack_rate(cfg, n_layers, d_ff, steps, warmup):
             "tokens_per_s": cfg.batch * cfg.seq_len / dt, "output_finite": bool(torch.isfinite(out.float()).all().item())}
 
 
-def time_forward(cfg, steps, warmup, calibrate_copy=False):
-    """K timed calls of rom_layer_forward on resident inputs.  Returns (ms per call, ms per call
-    without the stage events, per-stage dict)."""
+def _median(v):
+    v = sorted(v)
+    n = len(v)
+    return 0.0 if n == 0 else (v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2]))
+
+
+def time_forward(cfg, steps, warmup, with_balance=True):
+    """K timed calls of rom_layer_forward on resident inputs, bracketed by synchronize.  Every call
+    also sits between two events on the launch stream; the library records an event at every stage
+    boundary.  Returns a dict: median and mean milliseconds per call, the wall-clock mean, the same
+    K calls without stage events, and per-stage medians with achieved rates."""
     import torch
-    from paper_2506_18145_amd import RomLayer, rom_layer_forward, rom_profile_collect, rom_profile_enable
+    from paper_2506_18145_amd import (RomLayer, rom_layer_forward, rom_profile_collect_calls, rom_profile_enable)
     from rom_synth import make_input, make_weights
 
     layer = RomLayer(cfg, make_weights(cfg), device="cuda:0")
@@ -246,15 +262,20 @@ def time_forward(cfg, steps, warmup, calibrate_copy=False):
         step()
     torch.cuda.synchronize()
 
-    # timed region: K calls, stage events recorded by the library on the same stream
+    # timed region: K calls; events on the launch stream (torch's current stream is the one the
+    # binding hands to the library) around every call, stage events recorded by the library
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     rom_profile_enable(steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
+    evs[0].record()
+    for i in range(steps):
         step()
+        evs[i + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    stage_ms, n_calls = rom_profile_collect()
+    per_call = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+    calls = rom_profile_collect_calls(steps)
     rom_profile_enable(0)
 
     # the same K calls without the event records, for the record-keeping overhead
@@ -265,48 +286,175 @@ def time_forward(cfg, steps, warmup, calibrate_copy=False):
     torch.cuda.synchronize()
     elapsed_plain = time.perf_counter() - t1
 
-    # load-balance statistics (Eq. (16)) from the logits and counts the last call left behind
-    lg, ct = layer.ws_view("logits", B, L), layer.ws_view("counts", B, L)
-    from paper_2506_18145_amd import rom_balance_stats
-    stats = layer.balance_stats(lg, ct, 1e-3)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(50):
-        rom_balance_stats(layer.dims, lg, ct, B * L, 1e-3, stats[0], stats[1], stats[2], ws)
-    e1.record()
-    torch.cuda.synchronize()
-    counts = ct.cpu().tolist()
-    balance = {"us_per_call": e0.elapsed_time(e1) * 1e3 / 50, "loss_term_alpha_1e-3": float(stats[2].cpu()[0]),
-               "max_over_mean_count": max(counts) / (sum(counts) / len(counts))}
+    res = {"ms_median": _median(per_call), "ms_mean_wall": elapsed * 1e3 / steps,
+           "ms_mean_wall_without_stage_events": elapsed_plain * 1e3 / steps, "ms_min": min(per_call),
+           "ms_max": max(per_call)}
 
-    if calibrate_copy:
-        src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")     # 1 GiB
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
+    if with_balance:
+        # load-balance statistics (Eq. (16)) from the logits and counts the last call left behind
+        lg, ct = layer.ws_view("logits", B, L), layer.ws_view("counts", B, L)
+        from paper_2506_18145_amd import rom_balance_stats
+        stats = layer.balance_stats(lg, ct, 1e-3)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(50):
+            rom_balance_stats(layer.dims, lg, ct, B * L, 1e-3, stats[0], stats[1], stats[2], ws)
+        e1.record()
         torch.cuda.synchronize()
+        counts = ct.cpu().tolist()
+        res["balance"] = {"us_per_call": e0.elapsed_time(e1) * 1e3 / 50, "loss_term_alpha_1e-3": float(stats[2].cpu()[0]),
+                          "max_over_mean_count": max(counts) / (sum(counts) / len(counts)),
+                          "counts": counts}
 
     n_tok = B * L
     stages = {}
     for name, (bound, work) in stage_model(cfg).items():
-        avg_ms = stage_ms[name] / max(n_calls, 1)
-        if avg_ms <= 0 or work == 0:
-            stages[name] = {"ms": avg_ms}
+        ms = _median([c[name] for c in calls]) if calls else 0.0
+        if ms <= 0 or work == 0:
+            stages[name] = {"ms": ms}
             continue
         if bound == "mfma":
-            ach = work / (avg_ms * 1e-3) / 1e12
-            stages[name] = {"ms": avg_ms, "bound": "mfma", "achieved_tflops": ach,
-                            "frac": ach / PEAK_BF16_TFLOPS}
+            ach = work / (ms * 1e-3) / 1e12
+            stages[name] = {"ms": ms, "bound": "mfma", "achieved_tflops": ach, "frac": ach / PEAK_BF16_TFLOPS}
         else:
-            ach = work / (avg_ms * 1e-3) / 1e9
-            stages[name] = {"ms": avg_ms, "bound": "hbm", "achieved_gbs": ach, "frac": ach / PEAK_HBM_GBS}
+            ach = work / (ms * 1e-3) / 1e9
+            stages[name] = {"ms": ms, "bound": "hbm", "achieved_gbs": ach, "frac": ach / PEAK_HBM_GBS}
     # the scan is bound by plain ALU issue, not by HBM: also report it against the fp32 vector peak
     # (7 flops per (token, channel, state): dt*A, exp, dt*u*B, fma (2), C*h, one add of the reduction)
     if stages["scan_gate"].get("ms", 0) > 0:
         fl = 7.0 * n_tok * cfg.d_inner * cfg.d_state
         ach = fl / (stages["scan_gate"]["ms"] * 1e-3) / 1e12
-        stages["scan_gate"].update({"alu_tflops": ach, "alu_frac": ach / PEAK_ALU_FP32_TFLOPS})
-    return elapsed * 1e3 / steps, elapsed_plain * 1e3 / steps, stages, balance
+        stages["scan_gate"].update({"alu_tflops": ach, "alu_frac": ach / PEAK_ALU_FP32_TFLOPS,
+                                    "alu_peak_tflops": PEAK_ALU_FP32_TFLOPS})
+    res["stages"] = stages
+    return res
+
+
+def config_leg(name, steps, warmup):
+    """The same measurement on another of the paper-shaped workloads (beside the headline one)."""
+    from rom_synth import get_config
+    cfg = get_config(name)
+    r = time_forward(cfg, steps, warmup, with_balance=True)
+    n_tok = cfg.batch * cfg.seq_len
+    gemm = {k: v for k, v in r["stages"].items() if v.get("bound") == "mfma"}
+    fl = sum(v["achieved_tflops"] * v["ms"] for v in gemm.values())
+    ms = sum(v["ms"] for v in gemm.values())
+    return {"workload": f"{cfg.name}: B={cfg.batch}, L={cfg.seq_len}, d_model={cfg.d_model}, E={cfg.n_experts}, "
+                        f"top_k={cfg.top_k}, bf16", "ms_per_step": r["ms_median"], "tokens_per_s": n_tok / (r["ms_median"] * 1e-3),
+            "gemm_frac_of_mfma_peak": (fl / ms / PEAK_BF16_TFLOPS) if ms > 0 else None,
+            "scan_frac_of_hbm_peak": r["stages"]["scan_gate"].get("frac"),
+            "expert_counts_max_over_mean": r["balance"]["max_over_mean_count"], "stages": r["stages"]}
+
+
+# ------------------------------------------------------------------ HBM traffic of the dominant kernel
+def traffic_child(workload):
+    """Runs under rocprofv3 --pmc: a few forward calls and a few copies of known size."""
+    import torch
+    from paper_2506_18145_amd import RomLayer, rom_layer_forward, rom_profile_copy
+    from rom_synth import get_config, make_input, make_weights
+    cfg = get_config(workload)
+    layer = RomLayer(cfg, make_weights(cfg), device="cuda:0")
+    x = layer.to_device(make_input(cfg))
+    B, L = cfg.batch, cfg.seq_len
+    out = torch.empty_like(x)
+    ws = layer.workspace(B, L)
+    for _ in range(3):
+        rom_layer_forward(layer.dims, layer.weights, x, B, L, None, None, out, None, None, ws)
+    src = torch.ones(TRAFFIC_COPY_BYTES, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        rom_profile_copy(src, dst)
+    torch.cuda.synchronize()
+
+
+TRAFFIC_COPY_BYTES = 1 << 29      # 512 MiB read + 512 MiB written by the calibration copy
+
+
+def measure_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs of this script
+    (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each reading scaled by what the same counter
+    shows for the library's plain copy kernel of known size.  Runs the profiler as child processes
+    BEFORE this process touches the GPU.  Returns (bytes or None, detail dict)."""
+    import csv
+    import glob
+    import shutil
+    import subprocess
+    import tempfile
+    prof = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
+    if not os.path.exists(prof):
+        return None, {"note": "rocprofv3 not found"}
+    detail = {"command": "rocprofv3 --pmc <FETCH_SIZE|WRITE_SIZE> -d <tmp> -o p --output-format csv -- python3 bench.py "
+                         f"--traffic-child --workload {workload}", "copy_bytes": TRAFFIC_COPY_BYTES}
+    total = 0.0
+    for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+        tmp = tempfile.mkdtemp(prefix="rom_pmc_", dir="/tmp")
+        try:
+            env = dict(os.environ, TMPDIR="/tmp")
+            cmd = [prof, "--pmc", counter, "-d", tmp, "-o", "p", "--output-format", "csv", "--", "python3",
+                   os.path.join(ROOT, "bench.py"), "--traffic-child", "--workload", workload]
+            run = subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, timeout=240)
+            files = glob.glob(os.path.join(tmp, "**", "*counter_collection.csv"), recursive=True)
+            if run.returncode != 0 or not files:
+                return None, dict(detail, note=f"{counter} run failed (rc {run.returncode})")
+            kern, copy = [], []
+            for path in files:
+                for row in csv.DictReader(open(path)):
+                    if row.get("Counter_Name") != counter:
+                        continue
+                    if DOMINANT_KERNEL in row["Kernel_Name"]:
+                        kern.append(float(row["Counter_Value"]))
+                    elif "calib_copy_kernel" in row["Kernel_Name"]:
+                        copy.append(float(row["Counter_Value"]))
+            if not kern or not copy:
+                return None, dict(detail, note=f"{counter}: kernel rows not found")
+            kern_kib, copy_kib = sum(kern) / len(kern), sum(copy) / len(copy)
+            factor = (TRAFFIC_COPY_BYTES / 1024.0) / copy_kib
+            detail[counter] = {"kernel_kib_per_dispatch": kern_kib, "copy_kib_per_dispatch": copy_kib, "scale": factor}
+            total += kern_kib * 1024.0 * factor
+        except Exception as exc:      # a profiler problem must not cost the benchmark line
+            return None, dict(detail, note=f"{counter}: {type(exc).__name__}: {exc}")
+        finally:
+            shutil.rmtree(tmp, ignore_errors=True)
+    return total, detail
+
+
+def probe_rates():
+    """Issue rates of this chip as a wavefront sees them (ns and clocks at 2.4 GHz per instruction and
+    wavefront, at 1 / 2 / 4 / 8 wavefronts per SIMD), and the pipelined scan's tile without its memory
+    traffic.  Prints one JSON object."""
+    import torch
+    from paper_2506_18145_amd import rom_probe
+    scratch = torch.empty(256 * 8 * 256, dtype=torch.float32, device="cuda:0")
+
+    def run(kind, p0, p1, waves, iters):
+        rom_probe(kind, p0, p1, 256 * waves, 8, scratch)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        rom_probe(kind, p0, p1, 256 * waves, iters, scratch)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    out = {"note": "ns per instruction (or scan step) and wavefront; clk = ns x 2.4; waves = wavefronts per SIMD"}
+    ops = {0: "v_fma_f32", 1: "v_exp_f32", 2: "v_mov_b32_dpp"}
+    for op, name in ops.items():
+        for chains in (1, 8):
+            row = {}
+            for waves in (1, 2, 4, 8):
+                ns = run(0, op, chains, waves, 20000) * 1e6 / (20000 * 64)
+                row[f"waves={waves}"] = {"ns": round(ns, 3), "clk": round(ns * 2.4, 2), "simd_clk_per_inst": round(ns * 2.4 / waves, 2)}
+            out[f"{name}, {'dependent chain' if chains == 1 else '8 independent chains'}"] = row
+    parts = {(3, 0): "scan tile: decay/input + FMA chain", (6, 0): "scan tile: FMA chain + reduction/gate",
+             (7, 0): "scan tile: all three stages, registers only", (7, 1): "scan tile: all + LDS reads",
+             (7, 2): "scan tile: all + LDS reads + barrier"}
+    for (p0, p1), name in parts.items():
+        row = {}
+        for blocks in (1, 2):
+            ns = run(1, p0, p1, blocks, 256) * 1e6 / (256 * 64)
+            row[f"blocks_per_cu={blocks}"] = {"ns_per_step": round(ns, 2), "clk_per_step": round(ns * 2.4, 1)}
+        out[name] = row
+    print(json.dumps(out, indent=1))
 
 
 def main():
@@ -322,24 +470,36 @@ def main():
     ap.add_argument("--no-shared-xdt", action="store_true",
                     help="skip the extra measurement of the shared x/dt variant of the workload")
     ap.add_argument("--no-ffn", action="store_true", help="skip the extra FFN-MoE layer measurement")
+    ap.add_argument("--no-configs", action="store_true", help="skip the legs on the other paper-shaped workloads")
+    ap.add_argument("--no-traffic", action="store_true",
+                    help="skip the two rocprofv3 counter runs that measure the dominant kernel's HBM traffic")
     ap.add_argument("--stack-layers", type=int, default=48,
                     help="layers of the extra whole-stack measurement (0 = skip it)")
     ap.add_argument("--hybrid-layers", type=int, default=0,
                     help="also time a stack of this many (RoM block + FFN-MoE block) pairs (0 = skip)")
     ap.add_argument("--only-step", action="store_true",
                     help="run only the rom_step measurement and print its JSON object (for profiling)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run three plain 1 GiB device copies (a kernel of known traffic, for "
-                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--traffic-child", action="store_true", help=argparse.SUPPRESS)
+    ap.add_argument("--probe", action="store_true",
+                    help="print the chip's measured instruction issue rates and the scan tile's compute-only time, then exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    if args.traffic_child:
+        traffic_child(args.workload)
+        return
+    if args.probe:
+        probe_rates()
+        return
     if args.only_step:
         print(json.dumps({"decode_step": decode_step_rate()}))
         return
+
+    # counter runs first: they are child processes of a parent that has not touched the GPU yet
+    traffic, traffic_detail = (None, {"note": "skipped (--no-traffic)"}) if args.no_traffic else measure_traffic(args.workload)
 
     from dataclasses import replace
     from rom_synth import get_config
@@ -347,20 +507,31 @@ def main():
     cfg = get_config(args.workload)
     B, L = cfg.batch, cfg.seq_len
     n_tok = B * L
-    ms_per_step, ms_plain, stages, balance = time_forward(cfg, args.steps, args.warmup, args.calibrate_copy)
+    r = time_forward(cfg, args.steps, args.warmup)
+    stages = r["stages"]
     dom = stages["in_proj"]
-    roofline = {"kernel": "in_proj grouped GEMM (gemm_bf16_dma_kernel<256, 4, 2, 0>)", "bound": "mfma",
+    clock_ratio = COUNTER_CLOCK_GHZ_GEMM / NOMINAL_CLOCK_GHZ
+    roofline = {"kernel": f"in_proj grouped GEMM ({DOMINANT_KERNEL})", "bound": "mfma",
                 "achieved": dom.get("achieved_tflops"), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": dom.get("frac"),
-                "traffic": TRAFFIC_IN_PROJ_CFG2_BYTES if cfg.name == "cfg2" else None}
+                "traffic": traffic, "traffic_detail": traffic_detail,
+                "algorithmic_bytes": (n_tok * cfg.top_k * cfg.d_model + cfg.n_experts * 2 * cfg.d_inner * cfg.d_model
+                                      + n_tok * cfg.top_k * 2 * cfg.d_inner) * 2,
+                "clock_ghz_nominal": NOMINAL_CLOCK_GHZ, "clock_ghz_from_counters": COUNTER_CLOCK_GHZ_GEMM,
+                "peak_at_counter_clock": PEAK_BF16_TFLOPS * clock_ratio,
+                "frac_at_counter_clock": (dom["frac"] / clock_ratio) if dom.get("frac") else None,
+                "alu_peak_note": ALU_PEAK_NOTE}
 
     result = {
         "metric": "RoM layer fwd tokens/s at d=2048,L=16K; % MFMA peak (GEMM), % HBM BW (scan)",
-        "value": n_tok / (ms_per_step * 1e-3),
+        "value": n_tok / (r["ms_median"] * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
-        "ms_per_step_without_stage_events": ms_plain,
+        "ms_per_step": r["ms_median"],
+        "ms_per_step_is": "median over the K timed calls (HIP events around every call on the launch stream)",
+        "ms_per_step_mean_wall": r["ms_mean_wall"],
+        "ms_per_step_without_stage_events": r["ms_mean_wall_without_stage_events"],
+        "ms_per_step_min_max": [r["ms_min"], r["ms_max"]],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: RoM layer forward, B={B}, L={L}, d_model={cfg.d_model}, "
@@ -370,7 +541,7 @@ def main():
         "roofline": roofline,
         "stages": stages,
     }
-    result["balance_stats"] = balance
+    result["balance_stats"] = r.get("balance")
 
     def extra(name, fn):
         """A leg beside the headline measurement: its failure must not cost the headline line."""
@@ -379,14 +550,19 @@ def main():
         except Exception as exc:                      # reported, not hidden: the leg's object says what failed
             result[name] = {"error": f"{type(exc).__name__}: {exc}"}
 
+    if not args.no_configs:
+        for other in ("cfg1", "cfg3"):
+            if other != cfg.name:
+                extra(other, lambda other=other: config_leg(other, max(args.steps // 2, 5), args.warmup))
     if not args.no_shared_xdt:
         # the paper's default variant (Sec. 4.3, design choices): x and dt projections shared by all experts, so
         # those two stages are plain GEMMs; same shapes and inputs otherwise
         def shared_leg():
             shared = replace(cfg, name=cfg.name + "-shared-xdt", routed_xdt=False)
-            ms_s, _, stages_s, _ = time_forward(shared, max(args.steps // 2, 1), args.warmup)
-            return {"workload": f"{cfg.name} with one shared x/dt projection (E_x = 1)", "ms_per_step": ms_s,
-                    "tokens_per_s": n_tok / (ms_s * 1e-3), "stages_ms": {k: v["ms"] for k, v in stages_s.items()}}
+            rs = time_forward(shared, max(args.steps // 2, 1), args.warmup, with_balance=False)
+            return {"workload": f"{cfg.name} with one shared x/dt projection (E_x = 1)", "ms_per_step": rs["ms_median"],
+                    "tokens_per_s": n_tok / (rs["ms_median"] * 1e-3),
+                    "stages_ms": {k: v["ms"] for k, v in rs["stages"].items()}}
         extra("shared_xdt_variant", shared_leg)
     if not args.no_ffn:
         extra("ffn_moe", lambda: ffn_moe_rate(cfg, 2 * cfg.d_model, 20, 20))

@@ -333,7 +333,24 @@ ROM_API const char *rom_strerror(int code);
 #define ROM_STAGE_COUNT     9
 ROM_API int rom_profile_enable(int max_calls);
 ROM_API int rom_profile_collect(double *stage_ms, int *n_calls);
+/* The same per call: stage_ms (host) [max_calls][ROM_STAGE_COUNT] receives the milliseconds of
+ * every stage of each of the first max_calls recorded calls (0 for a stage that did not run). */
+ROM_API int rom_profile_collect_calls(double *stage_ms, int max_calls, int *n_calls);
+/* A kernel of known HBM traffic for scaling hardware counter readings: copies n_bytes (a multiple
+ * of 16; src, dst device pointers, 16-byte aligned, distinct) with one plain kernel
+ * (calib_copy_kernel): n_bytes read, n_bytes written. */
+ROM_API int rom_profile_copy(const void *src, void *dst, size_t n_bytes, void *hip_stream);
 ROM_API const char *rom_stage_name(int stage);
+/* Issue-rate probes behind `bench.py --probe` (what a wavefront of this chip issues per clock is
+ * measured, not assumed).  One asynchronous launch of n_blocks workgroups of 256 threads:
+ *   kind 0: p1 (1 or 8) independent chains of one instruction, p0 = 0 v_fma_f32, 1 v_exp_f32,
+ *           2 v_mov_b32_dpp; 64 * iters instructions per wavefront;
+ *   kind 1: the pipelined scan's tile on registers only; p0 = parts (bit 0 decay / input, bit 1 the
+ *           FMA chain, bit 2 reduction and gate: 3, 6 or 7), p1 = 0 registers only, 1 with the
+ *           tile's LDS reads, 2 also a barrier per tile; 64 * iters steps per wavefront.
+ * scratch: device, n_blocks * 1024 bytes.  Unknown combinations return ROM_E_INVAL. */
+ROM_API int rom_probe(int kind, int p0, int p1, int n_blocks, int iters, void *scratch, size_t scratch_bytes,
+              void *hip_stream);
 
 #ifdef __cplusplus
 }

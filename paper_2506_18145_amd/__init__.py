@@ -23,6 +23,9 @@ from .binding import (  # noqa: F401
     rom_stack_step,
     rom_layer_forward,
     rom_profile_collect,
+    rom_profile_collect_calls,
+    rom_profile_copy,
+    rom_probe,
     rom_profile_enable,
     rom_route,
     rom_route_workspace_bytes,

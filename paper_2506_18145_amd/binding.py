@@ -105,6 +105,13 @@ def load_library() -> ctypes.CDLL:
     lib.rom_profile_enable.argtypes = [ctypes.c_int]
     lib.rom_profile_collect.restype = ctypes.c_int
     lib.rom_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
+    lib.rom_profile_collect_calls.restype = ctypes.c_int
+    lib.rom_profile_collect_calls.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int,
+                                              ctypes.POINTER(ctypes.c_int)]
+    lib.rom_profile_copy.restype = ctypes.c_int
+    lib.rom_profile_copy.argtypes = [P, P, SZ, P]
+    lib.rom_probe.restype = ctypes.c_int
+    lib.rom_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, SZ, P]
     lib.rom_stage_name.restype = ctypes.c_char_p
     lib.rom_stage_name.argtypes = [ctypes.c_int]
     _lib = lib
@@ -278,6 +285,24 @@ def rom_profile_collect():
     n = ctypes.c_int(0)
     _check(load_library().rom_profile_collect(ms, ctypes.byref(n)), "rom_profile_collect")
     return {name: ms[i] for i, name in enumerate(STAGE_NAMES)}, n.value
+
+
+def rom_profile_collect_calls(max_calls: int):
+    """Per recorded call: {stage name: milliseconds}.  Returns a list of such dicts."""
+    buf = (ctypes.c_double * (max(max_calls, 1) * len(STAGE_NAMES)))()
+    n = ctypes.c_int(0)
+    _check(load_library().rom_profile_collect_calls(buf, max_calls, ctypes.byref(n)), "rom_profile_collect_calls")
+    k = len(STAGE_NAMES)
+    return [{name: buf[c * k + i] for i, name in enumerate(STAGE_NAMES)} for c in range(n.value)]
+
+
+def rom_profile_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    _check(load_library().rom_profile_copy(_ptr(src), _ptr(dst), _nbytes(src), _stream()), "rom_profile_copy")
+
+
+def rom_probe(kind: int, p0: int, p1: int, n_blocks: int, iters: int, scratch: torch.Tensor) -> None:
+    _check(load_library().rom_probe(kind, p0, p1, n_blocks, iters, _ptr(scratch), _nbytes(scratch), _stream()),
+           "rom_probe")
 
 
 class RomLayer:

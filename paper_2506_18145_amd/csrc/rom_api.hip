@@ -800,6 +800,54 @@ int rom_profile_collect(double *stage_ms, int *n_calls) {
   return ROM_OK;
 }
 
+int rom_profile_collect_calls(double *stage_ms, int max_calls, int *n_calls) {
+  if (!stage_ms || !n_calls || max_calls < 0) return ROM_E_INVAL;
+  const int n = g_prof.n_calls < max_calls ? g_prof.n_calls : max_calls;
+  *n_calls = n;
+  for (int c = 0; c < g_prof.n_calls; ++c) {
+    for (int i = 0; i < ROM_STAGE_COUNT; ++i) {
+      int &b = g_prof.begin_of[c * ROM_STAGE_COUNT + i], &e = g_prof.end_of[c * ROM_STAGE_COUNT + i];
+      float ms = 0.0f;
+      if (b >= 0 && e >= 0) {
+        if (hipEventSynchronize(g_prof.ev[e]) != hipSuccess) return ROM_E_HIP;
+        if (hipEventElapsedTime(&ms, g_prof.ev[b], g_prof.ev[e]) != hipSuccess) return ROM_E_HIP;
+      }
+      if (c < n) stage_ms[c * ROM_STAGE_COUNT + i] = ms;
+      b = e = -1;
+    }
+  }
+  g_prof.n_calls = 0;
+  return ROM_OK;
+}
+
+// plain copy of known traffic (n_bytes read, n_bytes written), 16 bytes per thread
+__global__ __launch_bounds__(256) void calib_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, int64_t n) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
+int rom_profile_copy(const void *src, void *dst, size_t n_bytes, void *hip_stream) {
+  if (!src || !dst || src == dst || n_bytes % 16 != 0 || !aligned16(src) || !aligned16(dst)) return ROM_E_INVAL;
+  if (n_bytes == 0) return ROM_OK;
+  const int64_t n = static_cast<int64_t>(n_bytes / 16);
+  if (ceil_div(n, 256) > 0x7fffffffll) return ROM_E_UNSUPPORTED;
+  hipLaunchKernelGGL(calib_copy_kernel, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0,
+                     static_cast<hipStream_t>(hip_stream), static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n);
+  return hipGetLastError() == hipSuccess ? ROM_OK : ROM_E_HIP;
+}
+
+int rom_probe(int kind, int p0, int p1, int n_blocks, int iters, void *scratch, size_t scratch_bytes,
+              void *hip_stream) {
+  if (!scratch || n_blocks < 1 || iters < 1 || scratch_bytes < static_cast<size_t>(n_blocks) * 256 * sizeof(float))
+    return ROM_E_INVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  float *out = static_cast<float *>(scratch);
+  const hipError_t e = kind == 0 ? launch_probe_issue(p0, p1, n_blocks, iters, out, s)
+                                 : launch_probe_scan(p0, p1, n_blocks, iters, out, s);
+  if (e == hipErrorInvalidValue) return ROM_E_INVAL;
+  return e == hipSuccess ? ROM_OK : ROM_E_HIP;
+}
+
 const char *rom_stage_name(int stage) {
   static const char *names[ROM_STAGE_COUNT] = {"route", "permute", "in_proj", "conv", "x_proj",
                                                "dt_proj", "scan_gate", "out_proj", "combine"};

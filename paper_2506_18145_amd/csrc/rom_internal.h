@@ -120,6 +120,10 @@ hipError_t launch_combine(int dtype, const void *op, const int32_t *inv_perm, co
                           void *out, int64_t n_tokens, int top_k, int d_model, const void *residual,
                           hipStream_t s);
 
+// timing probes (bench.py --probe): out is f32 scratch of n_blocks * 256 floats
+hipError_t launch_probe_issue(int op, int chains, int n_blocks, int iters, float *out, hipStream_t s);
+hipError_t launch_probe_scan(int parts, int lds, int n_blocks, int tiles, float *out, hipStream_t s);
+
 // ---------------------------------------------------------------- FFN-MoE (Eq. (14), (15))
 // a[p, 8b + t] = SiLU(h[p, 16b + t]) * h[p, 16b + 8 + t], t < 8: h's columns are blocks of 8 gate + 8 up
 // features (h T [n_rows, 2*d_ff], a T [n_rows, d_ff]; d_ff % 8 == 0)

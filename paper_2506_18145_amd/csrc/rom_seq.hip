@@ -920,6 +920,80 @@ __global__ __launch_bounds__(256) void rstd_sorted_kernel(const T *__restrict__ 
   if (lane == 0) rstd_sorted[p] = 1.0f / sqrtf(ss / static_cast<float>(d_model) + eps);
 }
 
+// ------------------------------------------------------------------ timing probes (bench.py --probe)
+// What a wavefront can issue, measured rather than assumed: chains of one instruction kind,
+// dependent or independent, at a chosen number of wavefronts per SIMD; and the pipelined scan's
+// tile with parts switched off and without its memory traffic.  Not on any product path.
+template <int CHAINS, int OP>   // OP 0: v_fma_f32, 1: v_exp_f32, 2: v_mov_b32_dpp (row broadcast)
+__global__ __launch_bounds__(256) void probe_issue_kernel(float *out, int iters, float a, float b) {
+  float acc[CHAINS];
+#pragma unroll
+  for (int c = 0; c < CHAINS; ++c) acc[c] = threadIdx.x * 1e-3f + c;
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int r = 0; r < 64 / CHAINS; ++r) {
+#pragma unroll
+      for (int c = 0; c < CHAINS; ++c) {
+        if (OP == 0) asm volatile("v_fma_f32 %0, %1, %0, %2" : "+v"(acc[c]) : "v"(a), "v"(b));
+        if (OP == 1) asm volatile("v_exp_f32 %0, %0" : "+v"(acc[c]));
+        if (OP == 2) asm volatile("v_mov_b32_dpp %0, %0 row_newbcast:3 row_mask:0xf bank_mask:0xf" : "+v"(acc[c]));
+      }
+    }
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int c = 0; c < CHAINS; ++c) s += acc[c];
+  out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+// PARTS as in scan_pipe_slot; LDS 0: registers only, 1: + the tile's LDS reads, 2: + a barrier and an LDS write per tile
+template <int PARTS, int LDS>
+__global__ __launch_bounds__(256) void probe_scan_kernel(float *out, int tiles) {
+  __shared__ ScanSmem sm;
+  __shared__ float g_tile[kScanTile][kChPitch];
+  const int tid = threadIdx.x, n = tid & 15, cl = tid >> 4;
+  for (int i = tid; i < static_cast<int>(sizeof(ScanSmem) / 4); i += 256) reinterpret_cast<float *>(&sm)[i] = 1e-3f * (i % 97);
+  for (int i = tid; i < kScanTile * kChPitch; i += 256) (&g_tile[0][0])[i] = 0.0f;
+  __syncthreads();
+  ScanPipeRegs r;
+  r.a2 = -0.5f - n; r.d_skip = 1.0f; r.h = 0.1f * n; r.y = 0.0f;
+  r.hi8 = (n & 8) != 0; r.hi4 = (n & 4) != 0; r.hi2 = (n & 2) != 0; r.hi1 = (n & 1) != 0;
+  for (int gi = 0; gi < kScanGroups; ++gi) {
+    r.dt_r[gi] = 0.01f * (gi + 1); r.u_r[gi] = 0.5f; r.dtu_r[gi] = 0.005f; r.z_r[gi] = 0.3f;
+    for (int j = 0; j < 16; ++j) { r.bv[gi][j] = 0.1f * j; r.cv[gi][j] = 0.2f; }
+  }
+  for (int j = 0; j < 16; ++j) { r.da[0][j] = r.da[1][j] = 0.99f; r.xx[0][j] = r.xx[1][j] = 0.01f; r.hs[0][j] = r.hs[1][j] = 0.0f; }
+  for (int j = 0; j < 8; ++j) r.ra[j] = 0.0f;
+  for (int j = 0; j < 4; ++j) r.rb[j] = 0.0f;
+  r.rc[0] = r.rc[1] = 0.0f;
+  for (int t = 0; t < tiles; ++t) {
+    if (LDS >= 1) {
+#pragma unroll
+      for (int gi = 0; gi < kScanGroups; ++gi) {
+        r.dt_r[gi] = sm.dt[gi * 16 + n][cl];
+        r.u_r[gi] = sm.u[gi * 16 + n][cl];
+        r.dtu_r[gi] = r.dt_r[gi] * r.u_r[gi];
+        scan_pipe_read16(r.bv[gi], &sm.bc[n][gi * 16]);
+        scan_pipe_read16(r.cv[gi], &sm.bc[16 + n][gi * 16]);
+        r.z_r[gi] = sm.zg[gi * 16 + n][cl];
+      }
+    } else {
+#pragma unroll
+      for (int gi = 0; gi < kScanGroups; ++gi) r.dt_r[gi] += r.h * 1e-30f;     // keeps the work inside the loop
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    ScanPipePhases<kScanGroups, PARTS>::run(r, g_tile, n, cl);
+    if (LDS >= 2) {
+      __syncthreads();
+      sm.dt[tid >> 2][(tid & 3) * 4] = g_tile[tid >> 2][(tid & 3) * 4] * 1e-9f + 0.01f;
+    }
+  }
+  float s = r.h + r.y;
+  for (int j = 0; j < 16; ++j) s += r.da[0][j] + r.da[1][j] + r.xx[0][j] + r.xx[1][j] + r.hs[0][j] + r.hs[1][j];
+  for (int j = 0; j < 8; ++j) s += r.ra[j];
+  out[blockIdx.x * 256 + tid] = s + g_tile[tid & 63][0];
+}
+
 inline dim3 grid1d(int64_t work, int block) { return dim3(static_cast<unsigned>(ceil_div(work, block))); }
 
 }  // namespace
@@ -1097,6 +1171,30 @@ hipError_t launch_scan_gate(int dtype, const void *u, const void *dt, const floa
   return scan_dispatch<float>(static_cast<const float *>(u), static_cast<const float *>(dt), bc,
                               static_cast<const float *>(z), ld_z, A_log, D, h_in, h_out,
                               static_cast<float *>(g), B, L, d_inner, chunk_q, chunk_p, s);
+}
+
+hipError_t launch_probe_issue(int op, int chains, int n_blocks, int iters, float *out, hipStream_t s) {
+  const dim3 grid(static_cast<unsigned>(n_blocks)), block(256);
+#define ROM_PROBE(C, OP)                                                                                 \
+  if (chains == C && op == OP) {                                                                         \
+    hipLaunchKernelGGL((probe_issue_kernel<C, OP>), grid, block, 0, s, out, iters, 0.999f, 1e-3f);       \
+    return hipGetLastError();                                                                            \
+  }
+  ROM_PROBE(1, 0) ROM_PROBE(8, 0) ROM_PROBE(1, 1) ROM_PROBE(8, 1) ROM_PROBE(1, 2) ROM_PROBE(8, 2)
+#undef ROM_PROBE
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_probe_scan(int parts, int lds, int n_blocks, int tiles, float *out, hipStream_t s) {
+  const dim3 grid(static_cast<unsigned>(n_blocks)), block(256);
+#define ROM_PROBE(P, M)                                                                     \
+  if (parts == P && lds == M) {                                                             \
+    hipLaunchKernelGGL((probe_scan_kernel<P, M>), grid, block, 0, s, out, tiles);           \
+    return hipGetLastError();                                                               \
+  }
+  ROM_PROBE(3, 0) ROM_PROBE(6, 0) ROM_PROBE(7, 0) ROM_PROBE(7, 1) ROM_PROBE(7, 2)
+#undef ROM_PROBE
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_combine(int dtype, const void *op, const int32_t *inv_perm, const float *gate,
