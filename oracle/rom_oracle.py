@@ -1,4 +1,4 @@
-"""CPU oracle for the Routing Mamba (RoM) layer forward pass and recurrent step.
+"""CPU oracle for the Routing Mamba (RoM) layer: forward pass, recurrent step, backward pass.
 
 TEST INFRASTRUCTURE ONLY.  This is a plain, slow, fp64 statement of what the
 layer computes, written from the paper's equations.  Only tests, the smoke
@@ -31,6 +31,10 @@ Readings of the paper taken here (each is also listed in the design notes):
     preceding RoM layer's router; its experts are SwiGLU MLPs with SiLU as the gate activation.
   * The pre-norm is RMSNorm with a learned scale and an eps inside the square root (the
     paper cites it without a formula or an eps); the skip adds the block's own input.
+  * Backward pass (training, Sec. 5.1): reverse-mode differentiation of the equations above with
+    the TopK indicator held constant; the router learns through the gate weights of Eq. (12).
+
+Every function here is pinned by tests/test_oracle_pins.py (nothing is "parity unpinned").
 """
 from __future__ import annotations
 
@@ -373,3 +377,184 @@ def ffn_moe_forward(x, w_gate_up, w_down, idx, gate, norm_w=None, eps=1e-5, skip
             if rows.size:
                 y[rows] += gate[rows, k:k + 1] * swiglu_expert(xin[rows], w_gate_up[i], w_down[i])
     return x + y if skip else y
+
+
+# --------------------------------------------------------------------------
+# Backward pass of the layer (training, Sec. 5.1): the gradient of a scalar loss with respect to
+# the layer input and every parameter, given d loss / d out.  Plain reverse-mode differentiation
+# of the equations above, stage by stage in reverse order.  Readings:
+#   * the TopK indicator of Eq. (9) is piecewise constant: it gets no gradient; the router is
+#     trained through the gate weights R_i = P_i of Eq. (12) only (straight-through selection,
+#     no jitter and no SparseMixer estimator, which the paper mentions as training options only);
+#   * gate_mode 1 differentiates the renormalisation over the selected K as well;
+#   * initial conv / scan states are constants (no gradient flows into a previous call).
+# --------------------------------------------------------------------------
+def gate_weights_backward(logits, idx, gate_mode, d_gate):
+    """d loss / d logits [N, E] from d loss / d gate [N, K] (Eq. (9): gate = softmax prob of the
+    selected experts, mode 1: divided by their sum)."""
+    p = softmax(logits)
+    idx64 = np.asarray(idx, np.int64)
+    d_gate = np.asarray(d_gate, F64)
+    sel = np.take_along_axis(p, idx64, axis=1)                   # P of the selected experts
+    if gate_mode == 1:
+        s = sel.sum(axis=1, keepdims=True)
+        gate = sel / s
+        d_sel = (d_gate - (d_gate * gate).sum(axis=1, keepdims=True)) / s
+    else:
+        d_sel = d_gate
+    d_p = np.zeros_like(p)
+    np.put_along_axis(d_p, idx64, d_sel, axis=1)                 # K distinct experts per token
+    # softmax: dl_e = P_e (dP_e - sum_j P_j dP_j)
+    return p * (d_p - (p * d_p).sum(axis=1, keepdims=True))
+
+
+def routed_linear_backward(inp, w, idx, d_out):
+    """Backward of routed_linear: returns (d_inp [N, D_in], d_w [E, D_out, D_in])."""
+    inp = np.asarray(inp, F64)
+    d_out = np.asarray(d_out, F64)
+    n_exp = w.shape[0]
+    d_w = np.zeros(w.shape, F64)
+    if n_exp == 1:
+        return d_out @ np.asarray(w[0], F64), (d_out.T @ inp)[None]
+    d_inp = np.zeros_like(inp)
+    for i in range(n_exp):
+        rows = np.nonzero((idx == i).any(axis=1))[0]
+        if rows.size:
+            d_inp[rows] += d_out[rows] @ np.asarray(w[i], F64)
+            d_w[i] = d_out[rows].T @ inp[rows]
+    return d_inp, d_w
+
+
+def silu_grad(v):
+    s = 1.0 / (1.0 + np.exp(-v))
+    return s * (1.0 + v * (1.0 - s))
+
+
+def causal_conv_silu_backward(h, conv_w, conv_b, d_u, conv_state=None):
+    """Backward of causal_conv_silu: returns (d_h [B, L, D_e], d_conv_w [D_e, k], d_conv_b [D_e])."""
+    h = np.asarray(h, F64)
+    bsz, length, d_e = h.shape
+    k = conv_w.shape[1]
+    cw = np.asarray(conv_w, F64)
+    hist = (np.zeros((bsz, k - 1, d_e), F64) if conv_state is None
+            else np.asarray(conv_state, F64).transpose(0, 2, 1))
+    ext = np.concatenate([hist, h], axis=1)
+    c = np.zeros((bsz, length, d_e), F64)
+    if conv_b is not None:
+        c += np.asarray(conv_b, F64)[None, None, :]
+    for j in range(k):
+        c += cw[None, None, :, j] * ext[:, j:j + length, :]
+    d_c = np.asarray(d_u, F64) * silu_grad(c)
+    d_ext = np.zeros_like(ext)
+    d_w = np.zeros_like(cw)
+    for j in range(k):
+        d_ext[:, j:j + length, :] += cw[None, None, :, j] * d_c
+        d_w[:, j] = (d_c * ext[:, j:j + length, :]).sum(axis=(0, 1))
+    return d_ext[:, k - 1:, :], d_w, d_c.sum(axis=(0, 1))
+
+
+def selective_scan_backward(u, dt, b_mat, c_mat, a, d_skip, d_y, h0=None):
+    """Backward of selective_scan (Eq. (5)): the forward recurrence is run once more keeping every
+    state, then the adjoint recurrence d_h[t-1] = exp(dt_t a) d_h[t] runs backwards in time.
+    Returns dict: d_u, d_dt [B, L, D_e]; d_b, d_c [B, L, D_s]; d_a [D_e, D_s]; d_d [D_e]."""
+    u = np.asarray(u, F64)
+    dt = np.asarray(dt, F64)
+    b_mat = np.asarray(b_mat, F64)
+    c_mat = np.asarray(c_mat, F64)
+    a = np.asarray(a, F64)
+    d_skip = np.asarray(d_skip, F64)
+    d_y = np.asarray(d_y, F64)
+    bsz, length, d_e = u.shape
+    d_s = a.shape[1]
+    h = (np.zeros((bsz, d_e, d_s), F64) if h0 is None else np.array(h0, F64, copy=True))
+    states = np.empty((length + 1, bsz, d_e, d_s), F64)
+    states[0] = h
+    for t in range(length):
+        decay = np.exp(dt[:, t, :, None] * a[None, :, :])
+        h = decay * h + (dt[:, t, :] * u[:, t, :])[:, :, None] * b_mat[:, t, None, :]
+        states[t + 1] = h
+    d_u = d_skip[None, None, :] * d_y
+    d_dt = np.zeros_like(dt)
+    d_b = np.zeros_like(b_mat)
+    d_c = np.zeros_like(c_mat)
+    d_a = np.zeros_like(a)
+    d_d = (d_y * u).sum(axis=(0, 1))
+    d_h = np.zeros((bsz, d_e, d_s), F64)
+    for t in range(length - 1, -1, -1):
+        d_c[:, t, :] = (d_y[:, t, :, None] * states[t + 1]).sum(axis=1)
+        d_h = d_h + d_y[:, t, :, None] * c_mat[:, t, None, :]          # y_t = C_t . h_t
+        decay = np.exp(dt[:, t, :, None] * a[None, :, :])
+        d_decay_arg = d_h * states[t] * decay                          # d / d (dt_t * a)
+        d_dt[:, t, :] += (d_decay_arg * a[None, :, :]).sum(axis=2)
+        d_a += (d_decay_arg * dt[:, t, :, None]).sum(axis=0)
+        inj = d_h * b_mat[:, t, None, :]                               # input term dt * B * u
+        d_dt[:, t, :] += inj.sum(axis=2) * u[:, t, :]
+        d_u[:, t, :] += inj.sum(axis=2) * dt[:, t, :]
+        d_b[:, t, :] = (d_h * (dt[:, t, :] * u[:, t, :])[:, :, None]).sum(axis=1)
+        d_h = d_h * decay                                              # adjoint of h_{t-1}
+    return {"d_u": d_u, "d_dt": d_dt, "d_b": d_b, "d_c": d_c, "d_a": d_a, "d_d": d_d, "d_h0": d_h}
+
+
+def rom_layer_backward(x, w, top_k, gate_mode, d_out, expert_idx=None):
+    """Gradients of the layer of rom_layer_forward (zero initial states).
+
+    x [B, L, D_m], d_out [B, L, D_m].  Returns a dict with d_x [B, L, D_m], one d_<name> per
+    parameter of `w` (same shapes; d_A_log is with respect to A_log, A = -exp(A_log)), and the
+    intermediate gradients d_g, d_dt (w.r.t. the softplus output), d_u, d_xz, d_gate, d_logits.
+    """
+    fwd = rom_layer_forward(x, w, top_k, gate_mode, expert_idx=expert_idx)
+    x = np.asarray(x, F64)
+    bsz, length, d_m = x.shape
+    n_tok = bsz * length
+    xt = x.reshape(n_tok, d_m)
+    idx, gate = fwd["expert_idx"], fwd["gate"]
+    d_e = w["w_out"].shape[2]
+    d_s = w["A_log"].shape[1]
+    r = w["w_dt"].shape[2]
+    d_o = np.asarray(d_out, F64).reshape(n_tok, d_m)
+    g, xz, ut, xdbl = fwd["g"], fwd["xz"], fwd["u"], fwd["xdbl"]
+    z = xz[:, d_e:]
+
+    # Eq. (12)/(13): out = sum_k gate_k * (g W_out[e_k]^T)
+    d_g = np.zeros((n_tok, d_e), F64)
+    d_gate = np.zeros((n_tok, top_k), F64)
+    d_w_out = np.zeros(w["w_out"].shape, F64)
+    for k in range(top_k):
+        col = idx[:, k:k + 1]
+        d_gate[:, k] = (d_o * routed_linear(g, w["w_out"], col)).sum(axis=1)
+        d_gk, d_wk = routed_linear_backward(g, w["w_out"], col, gate[:, k:k + 1] * d_o)
+        d_g += d_gk
+        d_w_out += d_wk
+    # Eq. (6)/(10): g = y * SiLU(z)
+    d_y = d_g * silu(z)
+    d_z = d_g * fwd["y"] * silu_grad(z)
+    # Eq. (5)
+    a = -np.exp(np.asarray(w["A_log"], F64))
+    dt = fwd["dt"]
+    sc = selective_scan_backward(ut.reshape(bsz, length, d_e), dt.reshape(bsz, length, d_e),
+                                 xdbl[:, r:r + d_s].reshape(bsz, length, d_s),
+                                 xdbl[:, r + d_s:].reshape(bsz, length, d_s), a, w["D"],
+                                 d_y.reshape(bsz, length, d_e))
+    d_dt = sc["d_dt"].reshape(n_tok, d_e)
+    # dt = softplus(pre): d pre = d dt * sigmoid(pre) = d dt * (1 - exp(-dt))
+    d_pre = d_dt * (1.0 - np.exp(-dt))
+    d_dt_low, d_w_dt = routed_linear_backward(xdbl[:, :r], w["w_dt"], idx, d_pre)
+    d_xdbl = np.concatenate([d_dt_low, sc["d_b"].reshape(n_tok, d_s), sc["d_c"].reshape(n_tok, d_s)], axis=1)
+    d_u_x, d_w_x = routed_linear_backward(ut, w["w_x"], idx, d_xdbl)
+    d_u = sc["d_u"].reshape(n_tok, d_e) + d_u_x
+    # Eq. (2)
+    d_h_pre, d_conv_w, d_conv_b = causal_conv_silu_backward(
+        xz[:, :d_e].reshape(bsz, length, d_e), w["conv_w"], w.get("conv_b"), d_u.reshape(bsz, length, d_e))
+    d_xz = np.concatenate([d_h_pre.reshape(n_tok, d_e), d_z], axis=1)
+    # Eq. (10)/(11)
+    d_x, d_w_in = routed_linear_backward(xt, w["w_in"], idx, d_xz)
+    # Eq. (9): the gates
+    d_logits = gate_weights_backward(fwd["logits"], idx, gate_mode, d_gate)
+    d_x = d_x + d_logits @ np.asarray(w["w_router"], F64)
+    return {
+        "d_x": d_x.reshape(bsz, length, d_m), "d_w_router": d_logits.T @ xt, "d_b_router": d_logits.sum(axis=0),
+        "d_w_in": d_w_in, "d_conv_w": d_conv_w, "d_conv_b": d_conv_b, "d_w_x": d_w_x, "d_w_dt": d_w_dt,
+        "d_dt_bias": d_pre.sum(axis=0), "d_A_log": sc["d_a"] * a, "d_D": sc["d_d"], "d_w_out": d_w_out,
+        "d_g": d_g, "d_y": d_y, "d_z": d_z, "d_dt": d_dt, "d_pre": d_pre, "d_u": d_u, "d_u_scan": sc["d_u"].reshape(n_tok, d_e),
+        "d_xdbl": d_xdbl, "d_xz": d_xz, "d_gate": d_gate, "d_logits": d_logits, "fwd": fwd,
+    }

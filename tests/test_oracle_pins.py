@@ -681,6 +681,157 @@ def test_ffn_moe_against_library_mlp_and_brute_force():
                                O.swiglu_expert(x, wgu[0], wd[0]), rtol=1e-12, atol=1e-13)
 
 
+# --------------------------------------------------------------------------
+# backward pass
+# --------------------------------------------------------------------------
+_PARAMS = ("w_router", "b_router", "w_in", "conv_w", "conv_b", "w_x", "w_dt", "dt_bias", "A_log", "D", "w_out")
+
+
+def _routed_layer_torch(x, w, idx, gate_mode):
+    """The layer of Eq. (9)-(13) from torch routines in float64 with a per-step loop for the
+    recurrence, on a given expert choice: an implementation independent of the oracle whose
+    gradients come from torch's reverse-mode differentiation."""
+    bsz, length, d_m = x.shape
+    n_exp, d_e = w["w_router"].shape[0], w["w_out"].shape[2]
+    d_s, r, k = w["A_log"].shape[1], w["w_dt"].shape[2], w["conv_w"].shape[1]
+    idx_t = torch.as_tensor(np.asarray(idx, np.int64)).reshape(bsz, length, -1)
+    onehot = F.one_hot(idx_t, n_exp).to(torch.float64)                 # [B, L, K, E]
+    ind = onehot.sum(dim=2)                                            # indicator 1[i in TopK]
+    logits = F.linear(x, w["w_router"], w["b_router"])
+    p = torch.softmax(logits, dim=-1)
+    sel = torch.gather(p, -1, idx_t)
+    gate = sel / sel.sum(-1, keepdim=True) if gate_mode == 1 else sel
+
+    def routed(inp, wt, weight_per_expert):
+        if wt.shape[0] == 1:
+            return F.linear(inp, wt[0])
+        return sum(weight_per_expert[..., e:e + 1] * F.linear(inp, wt[e]) for e in range(wt.shape[0]))
+
+    xz = routed(x, w["w_in"], ind)
+    h_pre, z = xz[..., :d_e], xz[..., d_e:]
+    c = F.conv1d(h_pre.transpose(1, 2), w["conv_w"][:, None, :], w["conv_b"], padding=k - 1, groups=d_e)[..., :length]
+    u = F.silu(c).transpose(1, 2)
+    xdbl = routed(u, w["w_x"], ind)
+    dt = F.softplus(routed(xdbl[..., :r], w["w_dt"], ind) + w["dt_bias"])
+    bm, cm = xdbl[..., r:r + d_s], xdbl[..., r + d_s:]
+    a = -torch.exp(w["A_log"])
+    h = torch.zeros(bsz, d_e, d_s, dtype=torch.float64)
+    ys = []
+    for t in range(length):
+        h = torch.exp(dt[:, t, :, None] * a) * h + (dt[:, t] * u[:, t])[:, :, None] * bm[:, t, None, :]
+        ys.append((h * cm[:, t, None, :]).sum(-1) + w["D"] * u[:, t])
+    g = torch.stack(ys, dim=1) * F.silu(z)
+    weights = (onehot * gate[..., None]).sum(dim=2)                    # R_i of Eq. (12) per expert
+    return sum(weights[..., e:e + 1] * F.linear(g, w["w_out"][e]) for e in range(n_exp))
+
+
+@pytest.mark.parametrize("top_k,gate_mode,routed,n_exp", [(1, 0, True, 3), (2, 1, True, 4), (2, 0, False, 3),
+                                                           (3, 1, True, 3), (1, 0, True, 1)])
+def test_backward_matches_reverse_mode_differentiation_of_library_layer(top_k, gate_mode, routed, n_exp):
+    cfg = tiny_cfg(top_k=top_k, gate_mode=gate_mode, routed_xdt=routed, n_experts=n_exp, seq_len=11)
+    w = _weights(cfg, seed_shift=top_k + 10 * gate_mode)
+    x = make_input(cfg)
+    rng = np.random.default_rng(17)
+    d_out = rng.standard_normal(x.shape)
+    res = O.rom_layer_backward(x, w, top_k, gate_mode, d_out)
+    idx = res["fwd"]["expert_idx"]
+    tw = {k: torch.tensor(np.asarray(w[k], np.float64), requires_grad=True) for k in _PARAMS}
+    tx = torch.tensor(np.asarray(x, np.float64), requires_grad=True)
+    out = _routed_layer_torch(tx, tw, idx, gate_mode)
+    assert np.allclose(out.detach().numpy(), res["fwd"]["out"], rtol=1e-11, atol=1e-13)
+    (out * torch.tensor(d_out)).sum().backward()
+    for name in _PARAMS:
+        want = tw[name].grad.numpy()
+        got = res["d_" + name]
+        assert got.shape == want.shape, name
+        assert np.max(np.abs(got - want)) <= 1e-10 * (1.0 + np.max(np.abs(want))), name
+    assert np.max(np.abs(res["d_x"] - tx.grad.numpy())) <= 1e-10 * (1.0 + np.max(np.abs(tx.grad.numpy())))
+    # every gradient is exercised: none of them is identically zero on this input
+    assert all(np.max(np.abs(res["d_" + n])) > 1e-6 for n in _PARAMS if not (n_exp == 1 and n.endswith("router")))
+    if n_exp == 1:      # one expert: the gate is 1 whatever the logits, the router gets no gradient
+        assert np.max(np.abs(res["d_w_router"])) < 1e-12 and np.max(np.abs(res["d_b_router"])) < 1e-12
+
+
+def test_backward_matches_central_differences_of_the_forward_oracle():
+    """d/d theta of sum(out * d_out) by central differences of rom_layer_forward at a fixed expert
+    choice, for sampled entries of x and of every parameter."""
+    cfg = tiny_cfg(top_k=2, gate_mode=1, n_experts=4, seq_len=9)
+    w = {k: (None if v is None else np.asarray(v, np.float64)) for k, v in _weights(cfg).items()}
+    x = np.asarray(make_input(cfg), np.float64)
+    rng = np.random.default_rng(23)
+    d_out = rng.standard_normal(x.shape)
+    res = O.rom_layer_backward(x, w, 2, 1, d_out)
+    idx = res["fwd"]["expert_idx"]
+
+    def loss(xx, ww):
+        return float((O.rom_layer_forward(xx, ww, 2, 1, expert_idx=idx)["out"] * d_out).sum())
+
+    eps = 1e-5
+    for name in _PARAMS + ("x",):
+        base = x if name == "x" else w[name]
+        grad = res["d_" + name]
+        scale = np.max(np.abs(grad))
+        for _ in range(8):
+            i = tuple(int(rng.integers(0, n)) for n in base.shape)
+            plus, minus = base.copy(), base.copy()
+            plus[i] += eps
+            minus[i] -= eps
+            if name == "x":
+                fd = (loss(plus, w) - loss(minus, w)) / (2 * eps)
+            else:
+                fd = (loss(x, dict(w, **{name: plus})) - loss(x, dict(w, **{name: minus}))) / (2 * eps)
+            assert abs(fd - grad[i]) <= 1e-6 * scale + 1e-8, (name, i, fd, grad[i])
+
+
+def test_scan_backward_closed_forms():
+    """Constant coefficients: y_T depends on u_s through C . a^(T-s) . dt B (+ D at s = T), so a
+    one-hot d_y at time T gives that as d_u; and the adjoint state after the last step back is
+    d_h0 = C a^T.  The D gradient is sum(d_y * u)."""
+    length, d_e, d_s = 9, 2, 3
+    rng = np.random.default_rng(31)
+    a = -rng.uniform(0.2, 1.5, (d_e, d_s))
+    dt0, b0, c0 = 0.3, rng.standard_normal(d_s), rng.standard_normal(d_s)
+    d_skip = rng.standard_normal(d_e)
+    u = rng.standard_normal((1, length, d_e))
+    dt = np.full((1, length, d_e), dt0)
+    bm, cm = np.tile(b0, (1, length, 1)), np.tile(c0, (1, length, 1))
+    t_hot = 6
+    d_y = np.zeros((1, length, d_e))
+    d_y[0, t_hot, :] = 1.0
+    r = O.selective_scan_backward(u, dt, bm, cm, a, d_skip, d_y)
+    decay = np.exp(dt0 * a)
+    for s_ in range(length):
+        want = np.zeros(d_e) if s_ > t_hot else dt0 * (c0 * b0 * decay ** (t_hot - s_)).sum(axis=1)
+        if s_ == t_hot:
+            want = want + d_skip
+        assert np.allclose(r["d_u"][0, s_], want, rtol=1e-12, atol=1e-14)
+    assert np.allclose(r["d_h0"][0], c0 * decay ** (t_hot + 1), rtol=1e-12)
+    assert np.allclose(r["d_d"], u[0, t_hot], rtol=1e-13)
+    # d_c[t] = d_y[t] * h[t]: only the hot step has one, and it is the forward state there
+    _, h_hot = O.selective_scan(u[:, :t_hot + 1], dt[:, :t_hot + 1], bm[:, :t_hot + 1], cm[:, :t_hot + 1], a, d_skip)
+    assert np.allclose(r["d_c"][0, t_hot], h_hot[0].sum(axis=0), rtol=1e-12)
+    assert np.all(r["d_c"][0, :t_hot] == 0) and np.all(r["d_c"][0, t_hot + 1:] == 0)
+
+
+def test_gate_backward_against_library_softmax():
+    rng = np.random.default_rng(37)
+    logits = rng.standard_normal((50, 6)) * 2
+    d_gate = rng.standard_normal((50, 3))
+    idx = O.topk_select(logits, 3)
+    for mode in (0, 1):
+        lt = torch.tensor(logits, requires_grad=True)
+        p = torch.softmax(lt, dim=1)
+        sel = torch.gather(p, 1, torch.as_tensor(idx.astype(np.int64)))
+        gate = sel / sel.sum(1, keepdim=True) if mode == 1 else sel
+        (gate * torch.tensor(d_gate)).sum().backward()
+        got = O.gate_weights_backward(logits, idx, mode, d_gate)
+        assert np.allclose(got, lt.grad.numpy(), rtol=1e-11, atol=1e-14)
+        assert np.allclose(got.sum(axis=1), 0.0, atol=1e-13)          # softmax is shift-invariant
+        if mode == 1:    # renormalised over all E selected = constant gate: no gradient at all
+            full = O.gate_weights_backward(logits, O.topk_select(logits, 6), 1, rng.standard_normal((50, 6)) * 0 + 1.0)
+            assert np.max(np.abs(full)) < 1e-13
+
+
 def test_softplus_and_silu_against_library():
     v = np.linspace(-40, 40, 161)
     assert np.allclose(O.softplus(v), F.softplus(torch.from_numpy(v), threshold=1e9).numpy(), rtol=1e-13)
