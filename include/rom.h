@@ -191,6 +191,45 @@ ROM_API int rom_step(const rom_dims *dims, const rom_weights *w, const void *x, 
 ROM_API int rom_step_static(const rom_dims *dims, const rom_weights *w, const void *x, int64_t B,
                     float *conv_state, float *ssm_state, void *out, void *hip_stream);
 
+/* ---- Backward pass of the layer (training, Sec. 5.1): the gradient of a scalar loss with respect to
+ * the layer input and every parameter, given d loss / d out.  Reverse-mode differentiation of
+ * Eq. (9)-(13) over Eq. (1)-(6); the TopK indicator of Eq. (9) is piecewise constant and gets no
+ * gradient, the router is trained through the gate weights R_i of Eq. (12) (no jitter, no SparseMixer
+ * estimator: the paper names those as options of its training runs only).  Zero initial conv / scan
+ * states, no state gradient.
+ * This build supports top_k == 1 (all of the paper's models); top_k > 1 returns ROM_E_UNSUPPORTED.
+ * All gradient buffers are f32 device memory of the parameter's shape, written (not accumulated):
+ * d_A_log is with respect to A_log.  d_b_router and d_conv_b may be NULL. */
+typedef struct rom_grads {
+  float *d_w_router;  /* [E, d_model]                          */
+  float *d_b_router;  /* [E] or NULL                           */
+  float *d_w_in;      /* [E, 2*d_inner, d_model]               */
+  float *d_conv_w;    /* [d_inner, d_conv]                     */
+  float *d_conv_b;    /* [d_inner] or NULL                     */
+  float *d_w_x;       /* [E_xdt, dt_rank + 2*d_state, d_inner] */
+  float *d_w_dt;      /* [E_xdt, d_inner, dt_rank]             */
+  float *d_dt_bias;   /* [d_inner]                             */
+  float *d_A_log;     /* [d_inner, d_state]                    */
+  float *d_D;         /* [d_inner]                             */
+  float *d_w_out;     /* [E, d_model, d_inner]                 */
+} rom_grads;
+
+/* Workspace bytes of rom_layer_backward (0 if dims are invalid or unsupported). */
+ROM_API size_t rom_backward_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L);
+
+/*   x      T [B, L, d_model]   the layer input of the forward call
+ *   d_out  T [B, L, d_model]   d loss / d out
+ *   d_x    T [B, L, d_model]   out: d loss / d x (must alias neither x nor d_out)
+ *   grads  host struct of device pointers, see above
+ *   ws     rom_backward_workspace_bytes(dims, B, L) bytes, 256-byte aligned
+ * The call runs the forward pass into its workspace first (activations are recomputed, nothing has
+ * to be kept from an earlier rom_layer_forward call), then the backward pass; asynchronous on
+ * hip_stream like every other call.  Results are deterministic (fixed summation orders, no atomics).
+ * B == 0 or L == 0 is a successful no-op. */
+ROM_API int rom_layer_backward(const rom_dims *dims, const rom_weights *w, const void *x, int64_t B, int64_t L,
+                       const void *d_out, void *d_x, const rom_grads *grads, void *ws, size_t ws_bytes,
+                       void *hip_stream);
+
 /* ---- Pre-norm residual block (appendix, architectures overview: every layer sits behind a
  * pre-norm and a skip connection):   out = x + RoM(RMSNorm(x)),
  *   RMSNorm(x)[n, :] = x[n, :] / sqrt(mean_d(x[n, d]^2) + eps) * norm_weight[:].

@@ -22,6 +22,8 @@ from .binding import (  # noqa: F401
     rom_stack_forward,
     rom_stack_step,
     rom_layer_forward,
+    rom_layer_backward,
+    rom_backward_workspace_bytes,
     rom_profile_collect,
     rom_profile_collect_calls,
     rom_profile_copy,

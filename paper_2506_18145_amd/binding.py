@@ -31,6 +31,12 @@ class _RomWeights(ctypes.Structure):
         "w_out")]
 
 
+class _RomGrads(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in (
+        "d_w_router", "d_b_router", "d_w_in", "d_conv_w", "d_conv_b", "d_w_x", "d_w_dt", "d_dt_bias", "d_A_log",
+        "d_D", "d_w_out")]
+
+
 class _RomBlock(ctypes.Structure):
     _fields_ = [("w", _RomWeights), ("norm_weight", ctypes.c_void_p)]
 
@@ -71,6 +77,11 @@ def load_library() -> ctypes.CDLL:
                                       P, P, P, P, P, P, SZ, P]
     lib.rom_step.restype = ctypes.c_int
     lib.rom_step.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64, P, P, P, P, SZ, P]
+    lib.rom_backward_workspace_bytes.restype = SZ
+    lib.rom_backward_workspace_bytes.argtypes = [ctypes.POINTER(RomDims), I64, I64]
+    lib.rom_layer_backward.restype = ctypes.c_int
+    lib.rom_layer_backward.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64, I64, P, P,
+                                       ctypes.POINTER(_RomGrads), P, SZ, P]
     lib.rom_step_static.restype = ctypes.c_int
     lib.rom_step_static.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64, P, P, P, P]
     F32 = ctypes.c_float
@@ -195,6 +206,21 @@ def rom_step_static(dims, weights, x, B, conv_state, ssm_state, out):
         ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(x), B, _ptr(conv_state),
         _ptr(ssm_state), _ptr(out), _stream())
     _check(code, "rom_step_static")
+
+
+def rom_backward_workspace_bytes(dims: RomDims, B: int, L: int) -> int:
+    return int(load_library().rom_backward_workspace_bytes(ctypes.byref(dims), B, L))
+
+
+def rom_layer_backward(dims, weights, x, B, L, d_out, d_x, grads, ws):
+    """grads: mapping d_<parameter> -> f32 tensor (d_b_router / d_conv_b may be missing or None)."""
+    gs = _RomGrads()
+    for name, _ in _RomGrads._fields_:
+        setattr(gs, name, _ptr(grads.get(name)))
+    code = load_library().rom_layer_backward(
+        ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(x), B, L, _ptr(d_out), _ptr(d_x),
+        ctypes.byref(gs), _ptr(ws), _nbytes(ws), _stream())
+    _check(code, "rom_layer_backward")
 
 
 def _nbytes(t) -> int:
@@ -330,6 +356,7 @@ class RomLayer:
             self.weights[name] = t.to(self.device).contiguous()
         self._ws: Optional[torch.Tensor] = None
         self._route_ws: Optional[torch.Tensor] = None
+        self._bwd_ws: Optional[torch.Tensor] = None
         self._block_weights: Optional[Dict[str, Optional[torch.Tensor]]] = None
 
     def block_weights(self, in_place: bool = False) -> Dict[str, Optional[torch.Tensor]]:
@@ -453,6 +480,23 @@ class RomLayer:
             out = torch.empty_like(x)
         rom_step(self.dims, self.weights, x, B, conv_state, ssm_state, out, self.workspace(max(B, 1), 1))
         return out
+
+    def backward(self, x: torch.Tensor, d_out: torch.Tensor):
+        """(d_x, {d_<parameter>: f32 tensor}) for the layer on input x and upstream gradient d_out."""
+        B, L, _ = x.shape
+        need = rom_backward_workspace_bytes(self.dims, max(B, 1), max(L, 1))
+        if need == 0:
+            raise RomError("rom_backward_workspace_bytes returned 0: unsupported dims (top_k must be 1)")
+        if self._bwd_ws is None or self._bwd_ws.numel() < need:
+            self._bwd_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        d_x = torch.empty_like(x)
+        grads = {}
+        for name, _ in _RomGrads._fields_:
+            wt = self.weights.get(name[2:])
+            if wt is not None:
+                grads[name] = torch.empty(wt.shape, dtype=torch.float32, device=self.device)
+        rom_layer_backward(self.dims, self.weights, x, B, L, d_out, d_x, grads, self._bwd_ws)
+        return d_x, grads
 
 
 class RomStack:

@@ -399,6 +399,47 @@ FfnPlan make_ffn_plan(const rom_dims *d, int32_t d_ff, int64_t n_tok) {
   return p;
 }
 
+// ---------------------------------------------------------------- backward pass
+struct BwdPlan {              // byte offsets behind the forward plan
+  size_t total, fwd_out, wt_out, wt_dt, wt_x, wt_in, dg_raw, d_gate, d_logits, d_pre, d_u_scan, d_xz, ckpt, bc_part,
+      d_bc, d_dt_low, d_xdbl, d_u_x, dx_in, conv_part, router_part;
+};
+
+BwdPlan make_bwd_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
+  BwdPlan p;
+  size_t off = make_plan(d, n_seq, seq_len).total;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off += (bytes + kAlign - 1) / kAlign * kAlign;
+    return at;
+  };
+  const size_t N = static_cast<size_t>(n_seq) * seq_len, E = d->n_experts, Ex = d->n_experts_xdt;
+  const size_t b = d->dtype == ROM_DTYPE_BF16 ? 2 : 4;
+  const size_t De = d->d_inner, Dm = d->d_model, R = d->dt_rank;
+  p.fwd_out = take(N * Dm * b);
+  p.wt_out = take(E * Dm * De * b);
+  p.wt_dt = take(Ex * De * R * b);
+  p.wt_x = take(Ex * (R + 32) * De * b);
+  p.wt_in = take(E * 2 * De * Dm * b);
+  p.dg_raw = take(N * De * b);
+  p.d_gate = take(N * 4);
+  p.d_logits = take(N * E * 4);
+  p.d_pre = take(N * De * b);
+  p.d_u_scan = take(N * De * b);
+  p.d_xz = take(N * 2 * De * b);
+  p.ckpt = take(scan_bwd_ckpt_bytes(seq_len, d->d_inner));
+  p.bc_part = take(scan_bwd_part_bytes(static_cast<int64_t>(N), d->d_inner));
+  p.d_bc = take(N * 32 * 4);
+  p.d_dt_low = take(N * R * 4);
+  p.d_xdbl = take(N * (R + 32) * b);
+  p.d_u_x = take(N * De * b);
+  p.dx_in = take(N * Dm * b);
+  p.conv_part = take(conv_bwd_partial_bytes(n_seq, seq_len, d->d_inner));
+  p.router_part = take(router_bwd_partial_bytes(static_cast<int64_t>(N), d->d_model, d->n_experts));
+  p.total = off;
+  return p;
+}
+
 // device address of `scratch` on the current device, looked up once per device
 constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mu;
@@ -743,6 +784,110 @@ int rom_step_static(const rom_dims *dims, const rom_weights *w, const void *x, i
   // nothing in the step's workspace has to start at zero: every region is written before it is read
   return forward_impl(dims, w, x, B, 1, conv_state, ssm_state, out, conv_state, ssm_state, ws, kStaticScratchBytes,
                       static_cast<hipStream_t>(hip_stream));
+}
+
+size_t rom_backward_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L) {
+  if (check_dims(dims) != ROM_OK || B < 0 || L < 0 || dims->top_k != 1) return 0;
+  return make_bwd_plan(dims, B > 0 ? B : 1, L > 0 ? L : 1).total;
+}
+
+int rom_layer_backward(const rom_dims *d, const rom_weights *w, const void *x, int64_t B, int64_t L, const void *d_out,
+                       void *d_x, const rom_grads *gr, void *ws, size_t ws_bytes, void *hip_stream) {
+  int rc = check_dims(d);
+  if (rc != ROM_OK) return rc;
+  rc = check_weights(d, w);
+  if (rc != ROM_OK) return rc;
+  if (d->top_k != 1) return ROM_E_UNSUPPORTED;
+  if (B < 0 || L < 0) return ROM_E_INVAL;
+  if (B == 0 || L == 0) return ROM_OK;
+  if (!x || !d_out || !d_x || !gr || !ws || d_x == x || d_x == d_out) return ROM_E_INVAL;
+  if (!aligned16(x) || !aligned16(d_out) || !aligned16(d_x) || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0)
+    return ROM_E_INVAL;
+  const float *need[] = {gr->d_w_router, gr->d_w_in, gr->d_conv_w, gr->d_w_x, gr->d_w_dt, gr->d_dt_bias, gr->d_A_log,
+                         gr->d_D, gr->d_w_out};
+  for (const float *ptr : need)
+    if (!ptr || !aligned16(ptr)) return ROM_E_INVAL;
+  if (B * L > (1ll << 24) || B > 65535) return ROM_E_UNSUPPORTED;      // grid limits of the reduction kernels
+  const BwdPlan bp = make_bwd_plan(d, B, L);
+  if (ws_bytes < bp.total) return ROM_E_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char *base = static_cast<char *>(ws);
+  auto at = [&](size_t off) { return base + off; };
+  const Plan p = make_plan(d, B, L);
+  const int64_t N = B * L;
+  const int E = d->n_experts, Ex = d->n_experts_xdt, De = d->d_inner, Dm = d->d_model, R = d->dt_rank;
+  const size_t eb = d->dtype == ROM_DTYPE_BF16 ? 2 : 4;
+  const bool routed_xdt = Ex > 1;
+
+  // activations: the forward pass into the front part of the workspace
+  rc = forward_impl(d, w, x, B, L, nullptr, nullptr, at(bp.fwd_out), nullptr, nullptr, ws, p.total, s);
+  if (rc != ROM_OK) return rc;
+  const int32_t *offsets = reinterpret_cast<const int32_t *>(at(p.offsets));
+  const int32_t *tok_of_pos = reinterpret_cast<const int32_t *>(at(p.tok_of_pos));
+  const float *gate = reinterpret_cast<const float *>(at(p.gate));                 // [N] at top-1
+  float *d_gate = reinterpret_cast<float *>(at(bp.d_gate));
+  float *d_logits = reinterpret_cast<float *>(at(bp.d_logits));
+
+  // transposed weights: d_inp = d_out W contracts over the row index of W
+  ROM_TRY(launch_transpose(d->dtype, w->w_out, at(bp.wt_out), E, Dm, De, s));          // -> [E][De][Dm]
+  ROM_TRY(launch_transpose(d->dtype, w->w_dt, at(bp.wt_dt), Ex, De, R, s));            // -> [Ex][R][De]
+  ROM_TRY(launch_transpose(d->dtype, w->w_x, at(bp.wt_x), Ex, R + 32, De, s));         // -> [Ex][De][R+32]
+  ROM_TRY(launch_transpose(d->dtype, w->w_in, at(bp.wt_in), E, 2 * De, Dm, s));        // -> [E][Dm][2De]
+
+  auto dgrad = [&](const void *A, int64_t lda, const void *Wt, int n_groups, int n_out, int k_in, void *C, int64_t ldc,
+                   int c_is_f32) {
+    GemmArgs ga;
+    memset(&ga, 0, sizeof(ga));
+    ga.dtype = d->dtype;
+    ga.A = A; ga.lda = lda; ga.a_span = N * lda;
+    ga.W = Wt; ga.N = n_out; ga.K = k_in;
+    ga.C = C; ga.ldc = ldc; ga.c_is_f32 = c_is_f32;
+    ga.M = N;
+    if (n_groups > 1) {
+      ga.n_groups = n_groups; ga.offsets = offsets; ga.a_rows = tok_of_pos; ga.c_rows = tok_of_pos;
+    } else {
+      ga.n_groups = 1;
+    }
+    return launch_grouped_gemm(ga, s);
+  };
+  auto wgrad = [&](const void *A, int64_t lda, int M, const void *Bm, int64_t ldb, int Nn, int n_groups,
+                   const float *scale, float *C) {
+    return launch_wgrad(d->dtype, A, lda, M, Bm, ldb, Nn, n_groups > 1 ? tok_of_pos : nullptr, scale,
+                        n_groups > 1 ? offsets : nullptr, n_groups, N, C, s);
+  };
+
+  // Eq. (12)/(13): out = gate * (W_out[e] g)
+  ROM_TRY(dgrad(d_out, Dm, at(bp.wt_out), E, De, Dm, at(bp.dg_raw), De, 0));           // dg_raw = W_out[e]^T d_out
+  ROM_TRY(launch_gate_backward(d->dtype, at(bp.dg_raw), at(p.g), N, De, d_gate, s));
+  ROM_TRY(wgrad(d_out, Dm, Dm, at(p.g), De, De, E, gate, gr->d_w_out));
+  // Eq. (5), (6): scan, gate, softplus
+  ROM_TRY(launch_scan_backward(d->dtype, at(p.u), at(p.dt), reinterpret_cast<const float *>(at(p.bc)),
+                               at(p.xz) + static_cast<size_t>(De) * eb, 2 * De, at(bp.dg_raw), gate, w->A_log, w->D, B, L,
+                               De, reinterpret_cast<float *>(at(bp.ckpt)), reinterpret_cast<float *>(at(bp.bc_part)),
+                               at(bp.d_pre), at(bp.d_u_scan), at(bp.d_xz) + static_cast<size_t>(De) * eb, 2 * De,
+                               reinterpret_cast<float *>(at(bp.d_bc)), gr->d_A_log, gr->d_D, gr->d_dt_bias, s));
+  // dt projection
+  ROM_TRY(dgrad(at(bp.d_pre), De, at(bp.wt_dt), routed_xdt ? E : 1, R, De, at(bp.d_dt_low), R, 1));
+  ROM_TRY(wgrad(at(bp.d_pre), De, De, at(p.dt_low), R, R, routed_xdt ? E : 1, nullptr, gr->d_w_dt));
+  // x projection
+  ROM_TRY(launch_pack_dxdbl(d->dtype, reinterpret_cast<const float *>(at(bp.d_dt_low)),
+                            reinterpret_cast<const float *>(at(bp.d_bc)), N, R, at(bp.d_xdbl), s));
+  ROM_TRY(dgrad(at(bp.d_xdbl), R + 32, at(bp.wt_x), routed_xdt ? E : 1, De, R + 32, at(bp.d_u_x), De, 0));
+  ROM_TRY(wgrad(at(bp.d_xdbl), R + 32, R + 32, at(p.u), De, De, routed_xdt ? E : 1, nullptr, gr->d_w_x));
+  // Eq. (2): conv + SiLU; writes the conv half of d_xz
+  ROM_TRY(launch_conv_backward(d->dtype, at(p.xz), 2 * De, w->conv_w, w->conv_b, at(bp.d_u_scan), at(bp.d_u_x), B, L, De,
+                               at(bp.d_xz), 2 * De, reinterpret_cast<float *>(at(bp.conv_part)), gr->d_conv_w,
+                               gr->d_conv_b, s));
+  // Eq. (10)/(11): in / gate projection
+  ROM_TRY(dgrad(at(bp.d_xz), 2 * De, at(bp.wt_in), E, Dm, 2 * De, at(bp.dx_in), Dm, 0));
+  ROM_TRY(wgrad(at(bp.d_xz), 2 * De, 2 * De, x, Dm, Dm, E, nullptr, gr->d_w_in));
+  // Eq. (9): the router through the gate weights
+  ROM_TRY(launch_router_backward(d->dtype, reinterpret_cast<const float *>(at(p.logits)),
+                                 reinterpret_cast<const int32_t *>(at(p.expert_idx)), d_gate, x, N, Dm, E, 1,
+                                 d->gate_mode, d_logits, reinterpret_cast<float *>(at(bp.router_part)), gr->d_w_router,
+                                 gr->d_b_router, s));
+  ROM_TRY(launch_dx_finish(d->dtype, at(bp.dx_in), d_logits, w->w_router, N, Dm, E, d_x, s));
+  return ROM_OK;
 }
 
 const char *rom_strerror(int code) {

@@ -1,0 +1,714 @@
+// Backward pass of the RoM layer's sequence part and the small gradient kernels around the
+// grouped GEMMs (training, Sec. 5.1): adjoint of the selective scan of Eq. (5) with the gate of
+// Eq. (6)/(13) and the softplus of the time step folded in, adjoint of the causal conv + SiLU of
+// Eq. (2), gradient of the gate weights of Eq. (9)/(12), and the gather / transpose kernels that
+// bring activations into the layout the weight-gradient GEMMs contract over.
+// Correct-first: plain ALU kernels, deterministic (fixed summation orders, no atomics).
+#include "rom_internal.h"
+
+namespace rom {
+
+namespace {
+
+template <int CTRL> __device__ __forceinline__ float dpp(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+// sum of v over the 16 lanes of a DPP row, in every lane (fixed order)
+__device__ __forceinline__ float row_sum16(float v) {
+#pragma clang fp contract(off)
+  v = dpp<0x140>(v) + v;      // row_mirror
+  v = dpp<0x141>(v) + v;      // row_half_mirror
+  v = dpp<0x1B>(v) + v;       // quad_perm [3,2,1,0]
+  v = dpp<0xB1>(v) + v;       // quad_perm [1,0,3,2]
+  return v;
+}
+__device__ __forceinline__ float sigmoid_f32(float v) { return fast_rcp(1.0f + fast_exp2(-1.44269504088896341f * v)); }
+
+inline dim3 grid1d(int64_t work, int block) { return dim3(static_cast<unsigned>(ceil_div(work, block))); }
+
+// ------------------------------------------------------------------ adjoint of the selective scan
+// Same lane = (channel, state) layout as the forward kernel: a 256-thread block owns 16 channels
+// and walks every sequence of the batch, one after the other (the per-channel parameter gradients
+// accumulate in registers in a fixed order).  Per sequence:
+//   pass 1 (forward in time): the state recurrence alone, leaving the state at the start of every
+//           64-step tile in the checkpoint buffer;
+//   pass 2 (backward in time, tile by tile): the tile's states are recomputed from its checkpoint
+//           and kept in registers, then the adjoint recurrence d_h[t-1] = exp(dt_t a) d_h[t] walks
+//           the tile backwards.
+// Sums over the 16 states of a channel (d_dt, d_u, y) are DPP row sums; sums over the block's 16
+// channels (d_B, d_C) go through LDS in channel order; the sum of those over the channel groups of
+// the whole layer is left to bwd_reduce_bc_kernel (per-block partial rows in global memory).
+constexpr int kBwdTile = 64, kBwdCh = 16, kBwdPitch = kBwdCh + 1, kBwdGroup = 8;
+
+struct BwdSmem {
+  float dt[kBwdTile][kBwdPitch], u[kBwdTile][kBwdPitch], z[kBwdTile][kBwdPitch], dg[kBwdTile][kBwdPitch];
+  float bc[kBwdTile][33];                    // B_0..15, C_0..15 of every step
+  float gate[kBwdTile];
+  float o_pre[kBwdTile][kBwdPitch], o_u[kBwdTile][kBwdPitch], o_z[kBwdTile][kBwdPitch];   // outputs of the tile
+  float part_b[kBwdGroup][kBwdCh][17], part_c[kBwdGroup][kBwdCh][17];   // [step in group][channel][state] terms of d_B, d_C
+};
+
+template <typename T>
+__device__ __forceinline__ void bwd_load_tile(BwdSmem &sm, const T *u_b, const T *dt_b, const T *z_b, int64_t ld_z,
+                                              const T *dg_b, const float *bc_b, const float *gate_b, int64_t t0,
+                                              int64_t t_end, int d_inner, int tid, bool full) {
+  // thread -> (step row, channel) for the four [64][16] tensors, four rounds
+  for (int i = tid; i < kBwdTile * kBwdCh; i += 256) {
+    const int row = i / kBwdCh, c = i % kBwdCh;
+    const int64_t t = t0 + row;
+    const bool ok = t < t_end;
+    sm.dt[row][c] = ok ? to_f32(dt_b[t * d_inner + c]) : 0.0f;
+    sm.u[row][c] = ok ? to_f32(u_b[t * d_inner + c]) : 0.0f;
+    if (full) {
+      sm.z[row][c] = ok ? to_f32(z_b[t * ld_z + c]) : 0.0f;
+      sm.dg[row][c] = ok ? to_f32(dg_b[t * d_inner + c]) : 0.0f;
+    }
+  }
+  for (int i = tid; i < kBwdTile * 32; i += 256) {
+    const int row = i / 32, c = i % 32;
+    const int64_t t = t0 + row;
+    sm.bc[row][c] = t < t_end ? bc_b[t * 32 + c] : 0.0f;
+  }
+  if (full && tid < kBwdTile) {
+    const int64_t t = t0 + tid;
+    sm.gate[tid] = t < t_end ? (gate_b ? gate_b[t] : 1.0f) : 0.0f;
+  }
+}
+
+// grid: d_inner / 16 blocks.  ckpt: f32 [gridDim.x][n_tiles][16 channels][16 states] (one sequence at a time).
+// d_bc_part: f32 [gridDim.x][N][32].  Outputs d_pre (w.r.t. the softplus argument), d_u, d_z have type T.
+template <typename T>
+__global__ __launch_bounds__(256) void scan_bwd_kernel(
+    const T *__restrict__ u, const T *__restrict__ dt, const float *__restrict__ bc, const T *__restrict__ z,
+    int64_t ld_z, const T *__restrict__ dg, const float *__restrict__ gate, const float *__restrict__ A_log,
+    const float *__restrict__ D, int64_t n_seq, int64_t L, int d_inner, float *__restrict__ ckpt,
+    T *__restrict__ d_pre, T *__restrict__ d_u, T *__restrict__ d_z, int64_t ld_dz, float *__restrict__ d_bc_part,
+    float *__restrict__ d_A_log, float *__restrict__ d_D, float *__restrict__ d_dt_bias) {
+  __shared__ BwdSmem sm;
+  const int tid = threadIdx.x;
+  const int n = tid & 15, cl = tid >> 4;
+  const int c0 = blockIdx.x * kBwdCh, ch = c0 + cl;
+  const float a_nat = -__expf(A_log[static_cast<int64_t>(ch) * 16 + n]);      // A = -exp(A_log)
+  const float a2 = a_nat * 1.44269504088896341f;
+  const float d_skip = D[ch];
+  const int64_t n_tiles = (L + kBwdTile - 1) / kBwdTile;
+  float *ck = ckpt + static_cast<int64_t>(blockIdx.x) * n_tiles * 256;
+  const int64_t n_tok = n_seq * L;
+  float acc_a = 0.0f, acc_d = 0.0f, acc_bias = 0.0f;       // d_A (this lane's state), d_D, d_dt_bias (all lanes of a row alike)
+
+  for (int64_t b = 0; b < n_seq; ++b) {
+    const T *u_b = u + b * L * d_inner + c0;
+    const T *dt_b = dt + b * L * d_inner + c0;
+    const T *z_b = z + b * L * ld_z + c0;
+    const T *dg_b = dg + b * L * d_inner + c0;
+    const float *bc_b = bc + b * L * 32;
+    const float *gate_b = gate ? gate + b * L : nullptr;
+
+    // ---- pass 1: checkpoints
+    float h = 0.0f;
+    for (int64_t ti = 0; ti < n_tiles; ++ti) {
+      ck[ti * 256 + tid] = h;
+      __syncthreads();
+      bwd_load_tile<T>(sm, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ti * kBwdTile, L, d_inner, tid, false);
+      __syncthreads();
+      if (ti + 1 < n_tiles) {          // the last tile's end state is not needed
+#pragma unroll 8
+        for (int s = 0; s < kBwdTile; ++s) {
+          const float dts = sm.dt[s][cl];
+          h = fmaf(fast_exp2(dts * a2), h, dts * sm.u[s][cl] * sm.bc[s][n]);
+        }
+      }
+    }
+
+    // ---- pass 2: tiles in reverse
+    float dh = 0.0f;
+    for (int64_t ti = n_tiles - 1; ti >= 0; --ti) {
+      const int64_t t0 = ti * kBwdTile;
+      __syncthreads();
+      bwd_load_tile<T>(sm, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, t0, L, d_inner, tid, true);
+      __syncthreads();
+      float hs[kBwdTile + 1], da[kBwdTile];
+      hs[0] = ck[ti * 256 + tid];
+#pragma unroll
+      for (int s = 0; s < kBwdTile; ++s) {
+        const float dts = sm.dt[s][cl];
+        da[s] = fast_exp2(dts * a2);
+        hs[s + 1] = fmaf(da[s], hs[s], dts * sm.u[s][cl] * sm.bc[s][n]);
+      }
+#pragma unroll
+      for (int grp = kBwdTile / kBwdGroup - 1; grp >= 0; --grp) {
+#pragma unroll
+        for (int j = kBwdGroup - 1; j >= 0; --j) {
+          const int s = grp * kBwdGroup + j;
+          const float dts = sm.dt[s][cl], us = sm.u[s][cl], zs = sm.z[s][cl];
+          const float bn = sm.bc[s][n], cn = sm.bc[s][16 + n];
+          const float sig = sigmoid_f32(zs);
+          const float silu_z = zs * sig;
+          const float dgs = sm.dg[s][cl] * sm.gate[s];            // d loss / d g (gate weight of Eq. (12) applied)
+          const float dy = dgs * silu_z;
+          const float y = row_sum16(cn * hs[s + 1]) + d_skip * us;
+          dh = fmaf(cn, dy, dh);                                  // y_t = C_t . h_t
+          const float darg = dh * hs[s] * da[s];                  // d / d (dt_t * A)
+          const float inj = dh * bn;                              // input term dt * B * u
+          const float ddt = row_sum16(fmaf(darg, a_nat, inj * us));
+          const float du = fmaf(row_sum16(inj), dts, d_skip * dy);
+          acc_a = fmaf(darg, dts, acc_a);
+          sm.part_b[j][cl][n] = dh * dts * us;
+          sm.part_c[j][cl][n] = dy * hs[s + 1];
+          dh *= da[s];
+          if (n == 0) {
+            // dt = softplus(pre): d pre = d dt * sigmoid(pre) = d dt * (1 - exp(-dt))
+            const float dpre = ddt * (1.0f - fast_exp2(-1.44269504088896341f * dts));
+            sm.o_pre[s][cl] = dpre;
+            sm.o_u[s][cl] = du;
+            sm.o_z[s][cl] = dgs * y * sig * (1.0f + zs * (1.0f - sig));
+            acc_bias += dpre;
+            acc_d = fmaf(dy, us, acc_d);
+          }
+        }
+        __syncthreads();
+        // d_B, d_C of this group's steps: sum over the block's channels in channel order
+        {
+          const int j = tid / 32, c = tid % 32;              // 8 steps x 32 values = 256 threads
+          const float(*src)[kBwdCh][17] = c < 16 ? sm.part_b : sm.part_c;
+          float tot = 0.0f;
+#pragma unroll
+          for (int k = 0; k < kBwdCh; ++k) tot += src[j][k][c & 15];
+          const int64_t t = t0 + grp * kBwdGroup + j;
+          if (t < L) d_bc_part[(static_cast<int64_t>(blockIdx.x) * n_tok + b * L + t) * 32 + c] = tot;
+        }
+        __syncthreads();
+      }
+      // the tile's per-channel outputs
+      for (int i = tid; i < kBwdTile * kBwdCh; i += 256) {
+        const int row = i / kBwdCh, c = i % kBwdCh;
+        const int64_t t = t0 + row;
+        if (t < L) {
+          const int64_t at = (b * L + t) * d_inner + c0 + c;
+          d_pre[at] = from_f32<T>(sm.o_pre[row][c]);
+          d_u[at] = from_f32<T>(sm.o_u[row][c]);
+          d_z[(b * L + t) * ld_dz + c0 + c] = from_f32<T>(sm.o_z[row][c]);
+        }
+      }
+    }
+  }
+  d_A_log[static_cast<int64_t>(ch) * 16 + n] = acc_a * a_nat;      // d A_log = d A * A
+  if (n == 0) {
+    d_D[ch] = acc_d;
+    d_dt_bias[ch] = acc_bias;
+  }
+}
+
+// d_bc[t, :] = sum over the channel-group partials, in group order
+__global__ __launch_bounds__(256) void bwd_reduce_bc_kernel(const float *__restrict__ part, int n_parts, int64_t n_tok,
+                                                            float *__restrict__ d_bc) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i >= n_tok * 32) return;
+  float tot = 0.0f;
+  for (int p = 0; p < n_parts; ++p) tot += part[static_cast<int64_t>(p) * n_tok * 32 + i];
+  d_bc[i] = tot;
+}
+
+// ------------------------------------------------------------------ gate weights, Eq. (9)/(12)
+// top-1: d_gate[n] = d_out[n, :] . (W_out[e_n] g[n, :]) = (W_out[e_n]^T d_out[n, :]) . g[n, :] = dg_raw[n, :] . g[n, :]
+// one wavefront per token
+template <typename T>
+__global__ __launch_bounds__(256) void gate_bwd_kernel(const T *__restrict__ dg_raw, const T *__restrict__ g,
+                                                       int64_t n_tok, int d_inner, float *__restrict__ d_gate) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) >> 6;
+  if (n >= n_tok) return;
+  float acc = 0.0f;
+  for (int c = lane; c < d_inner; c += 64)
+    acc = fmaf(to_f32(dg_raw[n * d_inner + c]), to_f32(g[n * d_inner + c]), acc);
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) acc += __shfl_xor(acc, o, 64);
+  if (lane == 0) d_gate[n] = acc;
+}
+
+// d_logits [N, E] from d_gate [N, K]: softmax over all E experts, gate = P of the selected
+// (gate_mode 1: divided by their sum).  One thread per token.
+__global__ __launch_bounds__(256) void router_bwd_kernel(const float *__restrict__ logits,
+                                                         const int32_t *__restrict__ expert_idx,
+                                                         const float *__restrict__ d_gate, int64_t n_tok, int n_experts,
+                                                         int top_k, int gate_mode, float *__restrict__ d_logits) {
+  const int64_t n = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (n >= n_tok) return;
+  const float *l = logits + n * n_experts;
+  float m = l[0];
+  for (int e = 1; e < n_experts; ++e) m = fmaxf(m, l[e]);
+  float den = 0.0f;
+  for (int e = 0; e < n_experts; ++e) den += __expf(l[e] - m);
+  const float inv = 1.0f / den;
+  // d P of the selected experts
+  float s_sel = 0.0f, dot = 0.0f;
+  for (int k = 0; k < top_k; ++k) {
+    const float p = __expf(l[expert_idx[n * top_k + k]] - m) * inv;
+    s_sel += p;
+    dot = fmaf(d_gate[n * top_k + k], p, dot);               // sum_k d_gate_k P_k
+  }
+  // mode 1: gate_k = P_k / S  ->  dP_k = (d_gate_k - sum_j d_gate_j gate_j) / S ;  mode 0: dP_k = d_gate_k
+  // (a single renormalised pick is the constant 1: its gradient is exactly zero, not rounding noise)
+  const float shift = gate_mode == 1 ? (top_k == 1 ? d_gate[n] : dot / s_sel) : 0.0f;
+  const float scale = gate_mode == 1 ? 1.0f / s_sel : 1.0f;
+  float pdp = 0.0f;                                          // sum_e P_e dP_e
+  for (int k = 0; k < top_k; ++k) {
+    const float p = __expf(l[expert_idx[n * top_k + k]] - m) * inv;
+    pdp = fmaf(p, (d_gate[n * top_k + k] - shift) * scale, pdp);
+  }
+  for (int e = 0; e < n_experts; ++e) {
+    float dp = 0.0f;
+    for (int k = 0; k < top_k; ++k)
+      if (expert_idx[n * top_k + k] == e) dp = (d_gate[n * top_k + k] - shift) * scale;
+    d_logits[n * n_experts + e] = __expf(l[e] - m) * inv * (dp - pdp);
+  }
+}
+
+// partial[chunk][e][d] = sum over the chunk's tokens of d_logits[n, e] * x[n, d]  (d = d_model is the
+// bias column: x = 1).  grid (ceil((d_model + 1) / 256), n_chunks); a thread owns one column.
+constexpr int kRouterChunk = 512;
+template <typename T>
+__global__ __launch_bounds__(256) void router_wgrad_partial_kernel(const float *__restrict__ d_logits,
+                                                                   const T *__restrict__ x, int64_t n_tok, int d_model,
+                                                                   int n_experts, float *__restrict__ partial) {
+  __shared__ float dl[64][64];                      // [token in round][expert]
+  const int d = blockIdx.x * 256 + threadIdx.x;
+  const int64_t n0 = static_cast<int64_t>(blockIdx.y) * kRouterChunk;
+  const int64_t n1 = n0 + kRouterChunk < n_tok ? n0 + kRouterChunk : n_tok;
+  float acc[64];
+#pragma unroll
+  for (int e = 0; e < 64; ++e) acc[e] = 0.0f;
+  for (int64_t r0 = n0; r0 < n1; r0 += 64) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < 64 * n_experts; i += 256) {
+      const int64_t n = r0 + i / n_experts;
+      dl[i / n_experts][i % n_experts] = n < n1 ? d_logits[n * n_experts + i % n_experts] : 0.0f;
+    }
+    __syncthreads();
+    if (d <= d_model) {
+      for (int i = 0; i < 64 && r0 + i < n1; ++i) {
+        const float xv = d < d_model ? to_f32(x[(r0 + i) * d_model + d]) : 1.0f;
+#pragma unroll
+        for (int e = 0; e < 64; ++e)
+          if (e < n_experts) acc[e] = fmaf(dl[i][e], xv, acc[e]);
+      }
+    }
+  }
+  if (d <= d_model)
+#pragma unroll
+    for (int e = 0; e < 64; ++e)
+      if (e < n_experts) partial[(static_cast<int64_t>(blockIdx.y) * n_experts + e) * (d_model + 1) + d] = acc[e];
+}
+
+__global__ __launch_bounds__(256) void router_wgrad_finish_kernel(const float *__restrict__ partial, int n_chunks,
+                                                                  int d_model, int n_experts,
+                                                                  float *__restrict__ d_w_router,
+                                                                  float *__restrict__ d_b_router) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_experts * (d_model + 1)) return;
+  const int e = i / (d_model + 1), d = i % (d_model + 1);
+  float tot = 0.0f;
+  for (int c = 0; c < n_chunks; ++c) tot += partial[static_cast<int64_t>(c) * n_experts * (d_model + 1) + i];
+  if (d < d_model) d_w_router[e * d_model + d] = tot;
+  else if (d_b_router) d_b_router[e] = tot;
+}
+
+// d_x[n, d] = dx_in[n, d] + sum_e d_logits[n, e] * W_r[e, d]
+template <typename T>
+__global__ __launch_bounds__(256) void dx_finish_kernel(const T *__restrict__ dx_in, const float *__restrict__ d_logits,
+                                                        const T *__restrict__ w_router, int64_t n_tok, int d_model,
+                                                        int n_experts, T *__restrict__ d_x) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i >= n_tok * d_model) return;
+  const int64_t n = i / d_model;
+  const int d = static_cast<int>(i % d_model);
+  float v = to_f32(dx_in[i]);
+  for (int e = 0; e < n_experts; ++e) v = fmaf(d_logits[n * n_experts + e], to_f32(w_router[e * d_model + d]), v);
+  d_x[i] = from_f32<T>(v);
+}
+
+// ------------------------------------------------------------------ adjoint of conv + SiLU, Eq. (2)
+// A thread owns one channel and a run of kConvBwdRun steps of one sequence.  c_t = b + sum_j w_j x_{t-3+j}
+// is recomputed, d_c_t = (du_a + du_b)_t * SiLU'(c_t); d_x_{t} = sum_j w_j d_c_{t+3-j} needs d_c of three
+// later steps (zero past the sequence end), so the thread runs three steps into the next run.
+// Per-run partial sums of d_w[i, j] = sum_t d_c_t x_{t-3+j} and d_b = sum_t d_c_t go to
+// partial[run][5][channel] and are added in run order by conv_bwd_finish_kernel.
+constexpr int kConvBwdRun = 128;
+template <typename T>
+__global__ __launch_bounds__(256) void conv_bwd_kernel(const T *__restrict__ xz, int64_t ld_xz,
+                                                       const float *__restrict__ conv_w,
+                                                       const float *__restrict__ conv_b, const T *__restrict__ du_a,
+                                                       const T *__restrict__ du_b, int64_t L, int d_inner,
+                                                       T *__restrict__ d_xpre, int64_t ld_dx,
+                                                       float *__restrict__ partial) {
+  const int ch = blockIdx.x * blockDim.x + threadIdx.x;
+  if (ch >= d_inner) return;
+  const int64_t b = blockIdx.z, run = blockIdx.y;
+  const int64_t t0 = run * kConvBwdRun;
+  const int64_t t1 = t0 + kConvBwdRun < L ? t0 + kConvBwdRun : L;
+  const float4 wv = *reinterpret_cast<const float4 *>(conv_w + static_cast<int64_t>(ch) * 4);
+  const float w[4] = {wv.x, wv.y, wv.z, wv.w};
+  const float bias = conv_b ? conv_b[ch] : 0.0f;
+  const T *xr = xz + b * L * ld_xz + ch;
+  const int64_t tok0 = b * L;
+  auto xin = [&](int64_t t) { return (t >= 0 && t < L) ? to_f32(xr[t * ld_xz]) : 0.0f; };
+  auto dc_at = [&](int64_t t) {            // d loss / d c_t (0 outside the sequence)
+    if (t < 0 || t >= L) return 0.0f;
+    const float c = bias + w[0] * xin(t - 3) + w[1] * xin(t - 2) + w[2] * xin(t - 1) + w[3] * xin(t);
+    const float sig = sigmoid_f32(c);
+    const float du = to_f32(du_a[(tok0 + t) * d_inner + ch]) + to_f32(du_b[(tok0 + t) * d_inner + ch]);
+    return du * sig * (1.0f + c * (1.0f - sig));
+  };
+  float acc_w[4] = {0.f, 0.f, 0.f, 0.f}, acc_b = 0.0f;
+  // d_c of t, t+1, t+2, t+3 slide along the run
+  float d0 = dc_at(t0), d1 = dc_at(t0 + 1), d2 = dc_at(t0 + 2);
+  for (int64_t t = t0; t < t1; ++t) {
+    const float d3 = dc_at(t + 3);
+    // x_t feeds c_t (tap 3), c_{t+1} (tap 2), c_{t+2} (tap 1), c_{t+3} (tap 0)
+    d_xpre[(tok0 + t) * ld_dx + ch] = from_f32<T>(w[3] * d0 + w[2] * d1 + w[1] * d2 + w[0] * d3);
+    acc_b += d0;
+    acc_w[0] = fmaf(d0, xin(t - 3), acc_w[0]);
+    acc_w[1] = fmaf(d0, xin(t - 2), acc_w[1]);
+    acc_w[2] = fmaf(d0, xin(t - 1), acc_w[2]);
+    acc_w[3] = fmaf(d0, xin(t), acc_w[3]);
+    d0 = d1; d1 = d2; d2 = d3;
+  }
+  const int64_t n_runs = gridDim.y;
+  float *dst = partial + ((b * n_runs + run) * 5) * d_inner + ch;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) dst[j * d_inner] = acc_w[j];
+  dst[4 * d_inner] = acc_b;
+}
+
+__global__ __launch_bounds__(256) void conv_bwd_finish_kernel(const float *__restrict__ partial, int64_t n_parts,
+                                                              int d_inner, float *__restrict__ d_conv_w,
+                                                              float *__restrict__ d_conv_b) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= 5 * d_inner) return;
+  const int j = i / d_inner, ch = i % d_inner;
+  float tot = 0.0f;
+  for (int64_t p = 0; p < n_parts; ++p) tot += partial[(p * 5 + j) * d_inner + ch];
+  if (j < 4) d_conv_w[ch * 4 + j] = tot;
+  else if (d_conv_b) d_conv_b[ch] = tot;
+}
+
+// ------------------------------------------------------------------ weight transposes for the input gradients
+// dst[e][c][r] = src[e][r][c]: the grouped GEMM contracts over the contiguous index of both operands,
+// and d_inp = d_out W contracts over W's row index.  32 x 32 tiles through LDS.
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ src, T *__restrict__ dst, int rows,
+                                                        int cols) {
+  __shared__ T tile[32][33];
+  const int64_t base = static_cast<int64_t>(blockIdx.z) * rows * cols;
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
+  for (int i = ty; i < 32; i += 8)
+    if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = src[base + static_cast<int64_t>(r0 + i) * cols + c0 + tx];
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8)
+    if (c0 + i < cols && r0 + tx < rows) dst[base + static_cast<int64_t>(c0 + i) * rows + r0 + tx] = tile[tx][i];
+}
+
+// d_xdbl [N, R + 32] (type T) = [ d_dt_low (f32 [N, R]) | d_bc (f32 [N, 32]) ]
+template <typename T>
+__global__ __launch_bounds__(256) void pack_dxdbl_kernel(const float *__restrict__ d_dt_low,
+                                                         const float *__restrict__ d_bc, int64_t n_tok, int dt_rank,
+                                                         T *__restrict__ d_xdbl) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int cols = dt_rank + 32;
+  if (i >= n_tok * cols) return;
+  const int64_t n = i / cols;
+  const int c = static_cast<int>(i % cols);
+  d_xdbl[i] = from_f32<T>(c < dt_rank ? d_dt_low[n * dt_rank + c] : d_bc[n * 32 + (c - dt_rank)]);
+}
+
+// ------------------------------------------------------------------ weight gradients
+//   d_W[e][m][n] = sum over the sorted positions p of expert e of s_p * A[a_row(p)][m] * B[b_row(p)][n]
+// (A = the gradient of the projection's output, B = its input, s = gate weight for the out projection).
+// Both operands are stored position-major, so the contraction index is the slow one: a 128 x 128
+// output tile walks the expert's positions in slabs of 32, each thread fetches 16-byte pieces
+// (eight consecutive m or n of one position) and scatters them transposed into LDS, from where the
+// MFMA fragments (eight consecutive positions of one m / n) are read.  fp32 result, fixed order.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+constexpr int kWgTile = 128, kWgSlab = 32, kWgPitch = kWgSlab + 8;     // halfs per LDS row (80 bytes: 16-byte aligned rows)
+
+__global__ __launch_bounds__(256) void wgrad_bf16_kernel(const bf16_t *__restrict__ A, int64_t lda, int M,
+                                                         const bf16_t *__restrict__ Bm, int64_t ldb, int N,
+                                                         const int32_t *__restrict__ rows,
+                                                         const float *__restrict__ row_scale,
+                                                         const int32_t *__restrict__ offsets, int64_t n_pos,
+                                                         float *__restrict__ C) {
+  __shared__ __attribute__((aligned(16))) bf16_t As[kWgTile][kWgPitch];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[kWgTile][kWgPitch];
+  const int e = blockIdx.z;
+  const int64_t p_lo = offsets ? offsets[e] : 0, p_hi = offsets ? offsets[e + 1] : n_pos;
+  const int m0 = blockIdx.y * kWgTile, n0 = blockIdx.x * kWgTile;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;                       // 2 x 2 waves, 64 x 64 each
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+  const int frag_row = lane & 31, frag_half = lane >> 5;
+  // staging: 32 positions x 16 pieces of 8 columns per operand = 512 pieces, two per thread
+  for (int64_t p0 = p_lo; p0 < p_hi; p0 += kWgSlab) {
+    __syncthreads();
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+      const int q = tid + rep * 256, pp = q / 16, piece = q % 16;
+      const int64_t p = p0 + pp;
+      const bool live = p < p_hi;
+      const int64_t r = live ? (rows ? rows[p] : p) : 0;
+      const float sc = (live && row_scale) ? row_scale[r] : 1.0f;
+      uint4 va = make_uint4(0, 0, 0, 0), vb = make_uint4(0, 0, 0, 0);
+      if (live && m0 + piece * 8 < M) va = *reinterpret_cast<const uint4 *>(A + r * lda + m0 + piece * 8);
+      if (live && n0 + piece * 8 < N) vb = *reinterpret_cast<const uint4 *>(Bm + r * ldb + n0 + piece * 8);
+      const unsigned int *wa = &va.x, *wb = &vb.x;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float lo = __uint_as_float(wa[i] << 16), hi = __uint_as_float(wa[i] & 0xFFFF0000u);
+        if (row_scale) { lo *= sc; hi *= sc; }
+        As[piece * 8 + 2 * i][pp] = f32_to_bf16(lo);
+        As[piece * 8 + 2 * i + 1][pp] = f32_to_bf16(hi);
+        Bs[piece * 8 + 2 * i][pp] = static_cast<bf16_t>(wb[i] & 0xFFFFu);
+        Bs[piece * 8 + 2 * i + 1][pp] = static_cast<bf16_t>(wb[i] >> 16);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < kWgSlab / 16; ++kk) {
+      bf16x8_t fa[2], fb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        fa[i] = *reinterpret_cast<const bf16x8_t *>(&As[wm * 64 + i * 32 + frag_row][kk * 16 + frag_half * 8]);
+        fb[i] = *reinterpret_cast<const bf16x8_t *>(&Bs[wn * 64 + i * 32 + frag_row][kk * 16 + frag_half * 8]);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+  }
+  // the B fragment is the MFMA's row operand: this lane holds, for output row m = frag_row, the
+  // columns 8 q + 4 frag_half + r of each 32-wide tile in accumulator element 4 q + r
+  float *Ce = C + static_cast<int64_t>(e) * M * N;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int m = m0 + wm * 64 + i * 32 + frag_row;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = n0 + wn * 64 + j * 32 + q * 8 + frag_half * 4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (m < M && col + r < N) Ce[static_cast<int64_t>(m) * N + col + r] = acc[i][j][4 * q + r];
+      }
+  }
+}
+
+// the same contraction on the plain ALUs (fp32, or bf16 shapes the MFMA kernel does not take): 64 x 64 tiles
+template <typename T>
+__global__ __launch_bounds__(256) void wgrad_simple_kernel(const T *__restrict__ A, int64_t lda, int M,
+                                                           const T *__restrict__ Bm, int64_t ldb, int N,
+                                                           const int32_t *__restrict__ rows,
+                                                           const float *__restrict__ row_scale,
+                                                           const int32_t *__restrict__ offsets, int64_t n_pos,
+                                                           float *__restrict__ C) {
+  __shared__ float As[16][64 + 4], Bs[16][64 + 4];
+  const int e = blockIdx.z;
+  const int64_t p_lo = offsets ? offsets[e] : 0, p_hi = offsets ? offsets[e + 1] : n_pos;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+  float acc[4][4] = {};
+  for (int64_t p0 = p_lo; p0 < p_hi; p0 += 16) {
+    __syncthreads();
+    for (int i = tid; i < 16 * 64; i += 256) {
+      const int pp = i / 64, c = i % 64;
+      const int64_t p = p0 + pp;
+      float va = 0.0f, vb = 0.0f;
+      if (p < p_hi) {
+        const int64_t r = rows ? rows[p] : p;
+        const float sc = row_scale ? row_scale[r] : 1.0f;
+        if (m0 + c < M) va = to_f32(A[r * lda + m0 + c]) * sc;
+        if (n0 + c < N) vb = to_f32(Bm[r * ldb + n0 + c]);
+      }
+      As[pp][c] = va;
+      Bs[pp][c] = vb;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      float av[4], bv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { av[i] = As[k][ty * 4 + i]; bv[i] = Bs[k][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+    }
+  }
+  float *Ce = C + static_cast<int64_t>(e) * M * N;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + ty * 4 + i, col = n0 + tx * 4 + j;
+      if (m < M && col < N) Ce[static_cast<int64_t>(m) * N + col] = acc[i][j];
+    }
+}
+
+}  // namespace
+
+size_t scan_bwd_ckpt_bytes(int64_t L, int d_inner) {
+  return static_cast<size_t>(d_inner / kBwdCh) * static_cast<size_t>(ceil_div(L, kBwdTile)) * 256 * sizeof(float);
+}
+size_t scan_bwd_part_bytes(int64_t n_tok, int d_inner) {
+  return static_cast<size_t>(d_inner / kBwdCh) * static_cast<size_t>(n_tok) * 32 * sizeof(float);
+}
+
+hipError_t launch_scan_backward(int dtype, const void *u, const void *dt, const float *bc, const void *z, int64_t ld_z,
+                                const void *dg, const float *gate, const float *A_log, const float *D, int64_t B,
+                                int64_t L, int d_inner, float *ckpt, float *d_bc_part, void *d_pre, void *d_u, void *d_z,
+                                int64_t ld_dz, float *d_bc, float *d_A_log, float *d_D, float *d_dt_bias,
+                                hipStream_t s) {
+  const dim3 grid(static_cast<unsigned>(d_inner / kBwdCh));
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL((scan_bwd_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(u),
+                       static_cast<const bf16_t *>(dt), bc, static_cast<const bf16_t *>(z), ld_z,
+                       static_cast<const bf16_t *>(dg), gate, A_log, D, B, L, d_inner, ckpt, static_cast<bf16_t *>(d_pre),
+                       static_cast<bf16_t *>(d_u), static_cast<bf16_t *>(d_z), ld_dz, d_bc_part, d_A_log, d_D, d_dt_bias);
+  else
+    hipLaunchKernelGGL((scan_bwd_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(u),
+                       static_cast<const float *>(dt), bc, static_cast<const float *>(z), ld_z,
+                       static_cast<const float *>(dg), gate, A_log, D, B, L, d_inner, ckpt, static_cast<float *>(d_pre),
+                       static_cast<float *>(d_u), static_cast<float *>(d_z), ld_dz, d_bc_part, d_A_log, d_D, d_dt_bias);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t n_tok = B * L;
+  hipLaunchKernelGGL(bwd_reduce_bc_kernel, grid1d(n_tok * 32, 256), dim3(256), 0, s, d_bc_part, d_inner / kBwdCh, n_tok,
+                     d_bc);
+  return hipGetLastError();
+}
+
+hipError_t launch_gate_backward(int dtype, const void *dg_raw, const void *g, int64_t n_tok, int d_inner, float *d_gate,
+                                hipStream_t s) {
+  const dim3 grid = grid1d(n_tok * 64, 256);
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL((gate_bwd_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(dg_raw),
+                       static_cast<const bf16_t *>(g), n_tok, d_inner, d_gate);
+  else
+    hipLaunchKernelGGL((gate_bwd_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(dg_raw),
+                       static_cast<const float *>(g), n_tok, d_inner, d_gate);
+  return hipGetLastError();
+}
+
+size_t router_bwd_partial_bytes(int64_t n_tok, int d_model, int n_experts) {
+  return static_cast<size_t>(ceil_div(n_tok, kRouterChunk)) * n_experts * (d_model + 1) * sizeof(float);
+}
+
+hipError_t launch_router_backward(int dtype, const float *logits, const int32_t *expert_idx, const float *d_gate,
+                                  const void *x, int64_t n_tok, int d_model, int n_experts, int top_k, int gate_mode,
+                                  float *d_logits, float *partial, float *d_w_router, float *d_b_router, hipStream_t s) {
+  hipLaunchKernelGGL(router_bwd_kernel, grid1d(n_tok, 256), dim3(256), 0, s, logits, expert_idx, d_gate, n_tok, n_experts,
+                     top_k, gate_mode, d_logits);
+  const int n_chunks = static_cast<int>(ceil_div(n_tok, kRouterChunk));
+  const dim3 grid(static_cast<unsigned>(ceil_div(d_model + 1, 256)), static_cast<unsigned>(n_chunks));
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL((router_wgrad_partial_kernel<bf16_t>), grid, dim3(256), 0, s, d_logits,
+                       static_cast<const bf16_t *>(x), n_tok, d_model, n_experts, partial);
+  else
+    hipLaunchKernelGGL((router_wgrad_partial_kernel<float>), grid, dim3(256), 0, s, d_logits,
+                       static_cast<const float *>(x), n_tok, d_model, n_experts, partial);
+  hipLaunchKernelGGL(router_wgrad_finish_kernel, grid1d(static_cast<int64_t>(n_experts) * (d_model + 1), 256), dim3(256), 0,
+                     s, partial, n_chunks, d_model, n_experts, d_w_router, d_b_router);
+  return hipGetLastError();
+}
+
+hipError_t launch_dx_finish(int dtype, const void *dx_in, const float *d_logits, const void *w_router, int64_t n_tok,
+                            int d_model, int n_experts, void *d_x, hipStream_t s) {
+  const dim3 grid = grid1d(n_tok * d_model, 256);
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL((dx_finish_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(dx_in), d_logits,
+                       static_cast<const bf16_t *>(w_router), n_tok, d_model, n_experts, static_cast<bf16_t *>(d_x));
+  else
+    hipLaunchKernelGGL((dx_finish_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(dx_in), d_logits,
+                       static_cast<const float *>(w_router), n_tok, d_model, n_experts, static_cast<float *>(d_x));
+  return hipGetLastError();
+}
+
+size_t conv_bwd_partial_bytes(int64_t B, int64_t L, int d_inner) {
+  return static_cast<size_t>(B) * static_cast<size_t>(ceil_div(L, kConvBwdRun)) * 5 * d_inner * sizeof(float);
+}
+
+hipError_t launch_conv_backward(int dtype, const void *xz, int64_t ld_xz, const float *conv_w, const float *conv_b,
+                                const void *du_a, const void *du_b, int64_t B, int64_t L, int d_inner, void *d_xpre,
+                                int64_t ld_dx, float *partial, float *d_conv_w, float *d_conv_b, hipStream_t s) {
+  const int64_t n_runs = ceil_div(L, kConvBwdRun);
+  const dim3 grid(static_cast<unsigned>(ceil_div(d_inner, 256)), static_cast<unsigned>(n_runs), static_cast<unsigned>(B));
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL((conv_bwd_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(xz), ld_xz, conv_w,
+                       conv_b, static_cast<const bf16_t *>(du_a), static_cast<const bf16_t *>(du_b), L, d_inner,
+                       static_cast<bf16_t *>(d_xpre), ld_dx, partial);
+  else
+    hipLaunchKernelGGL((conv_bwd_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(xz), ld_xz, conv_w,
+                       conv_b, static_cast<const float *>(du_a), static_cast<const float *>(du_b), L, d_inner,
+                       static_cast<float *>(d_xpre), ld_dx, partial);
+  hipLaunchKernelGGL(conv_bwd_finish_kernel, grid1d(5 * d_inner, 256), dim3(256), 0, s, partial, B * n_runs, d_inner,
+                     d_conv_w, d_conv_b);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose(int dtype, const void *src, void *dst, int n_mats, int rows, int cols, hipStream_t s) {
+  const dim3 grid(static_cast<unsigned>(ceil_div(cols, 32)), static_cast<unsigned>(ceil_div(rows, 32)),
+                  static_cast<unsigned>(n_mats));
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL((transpose_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(src),
+                       static_cast<bf16_t *>(dst), rows, cols);
+  else
+    hipLaunchKernelGGL((transpose_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(src),
+                       static_cast<float *>(dst), rows, cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack_dxdbl(int dtype, const float *d_dt_low, const float *d_bc, int64_t n_tok, int dt_rank,
+                             void *d_xdbl, hipStream_t s) {
+  const dim3 grid = grid1d(n_tok * (dt_rank + 32), 256);
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL((pack_dxdbl_kernel<bf16_t>), grid, dim3(256), 0, s, d_dt_low, d_bc, n_tok, dt_rank,
+                       static_cast<bf16_t *>(d_xdbl));
+  else
+    hipLaunchKernelGGL((pack_dxdbl_kernel<float>), grid, dim3(256), 0, s, d_dt_low, d_bc, n_tok, dt_rank,
+                       static_cast<float *>(d_xdbl));
+  return hipGetLastError();
+}
+
+hipError_t launch_wgrad(int dtype, const void *A, int64_t lda, int M, const void *Bm, int64_t ldb, int N,
+                        const int32_t *rows, const float *row_scale, const int32_t *offsets, int n_groups,
+                        int64_t n_pos, float *C, hipStream_t s) {
+  const bool mfma = dtype == ROM_DTYPE_BF16 && M % 8 == 0 && N % 8 == 0 && lda % 8 == 0 && ldb % 8 == 0 &&
+                    reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(Bm) % 16 == 0;
+  if (mfma) {
+    const dim3 grid(static_cast<unsigned>(ceil_div(N, kWgTile)), static_cast<unsigned>(ceil_div(M, kWgTile)),
+                    static_cast<unsigned>(n_groups));
+    hipLaunchKernelGGL(wgrad_bf16_kernel, grid, dim3(256), 0, s, static_cast<const bf16_t *>(A), lda, M,
+                       static_cast<const bf16_t *>(Bm), ldb, N, rows, row_scale, offsets, n_pos, C);
+    return hipGetLastError();
+  }
+  const dim3 grid(static_cast<unsigned>(ceil_div(N, 64)), static_cast<unsigned>(ceil_div(M, 64)),
+                  static_cast<unsigned>(n_groups));
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL((wgrad_simple_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(A), lda, M,
+                       static_cast<const bf16_t *>(Bm), ldb, N, rows, row_scale, offsets, n_pos, C);
+  else
+    hipLaunchKernelGGL((wgrad_simple_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(A), lda, M,
+                       static_cast<const float *>(Bm), ldb, N, rows, row_scale, offsets, n_pos, C);
+  return hipGetLastError();
+}
+
+}  // namespace rom

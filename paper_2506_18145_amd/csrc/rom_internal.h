@@ -120,6 +120,39 @@ hipError_t launch_combine(int dtype, const void *op, const int32_t *inv_perm, co
                           void *out, int64_t n_tokens, int top_k, int d_model, const void *residual,
                           hipStream_t s);
 
+// ---------------------------------------------------------------- backward pass (rom_bwd.hip)
+size_t scan_bwd_ckpt_bytes(int64_t L, int d_inner);
+size_t scan_bwd_part_bytes(int64_t n_tok, int d_inner);
+// adjoint of scan + gate + softplus: dg is d loss / d (W_out^T d_out) per token, gate (f32 [N] or NULL = 1) the
+// weight it is multiplied by; writes d_pre (w.r.t. the softplus argument), d_u (scan part), d_z (pitch ld_dz), all of
+// the activation type, d_bc f32 [N, 32], and the parameter gradients d_A_log [d_inner, 16], d_D, d_dt_bias [d_inner]
+hipError_t launch_scan_backward(int dtype, const void *u, const void *dt, const float *bc, const void *z, int64_t ld_z,
+                                const void *dg, const float *gate, const float *A_log, const float *D, int64_t B,
+                                int64_t L, int d_inner, float *ckpt, float *d_bc_part, void *d_pre, void *d_u, void *d_z,
+                                int64_t ld_dz, float *d_bc, float *d_A_log, float *d_D, float *d_dt_bias,
+                                hipStream_t s);
+hipError_t launch_gate_backward(int dtype, const void *dg_raw, const void *g, int64_t n_tok, int d_inner, float *d_gate,
+                                hipStream_t s);
+size_t router_bwd_partial_bytes(int64_t n_tok, int d_model, int n_experts);
+hipError_t launch_router_backward(int dtype, const float *logits, const int32_t *expert_idx, const float *d_gate,
+                                  const void *x, int64_t n_tok, int d_model, int n_experts, int top_k, int gate_mode,
+                                  float *d_logits, float *partial, float *d_w_router, float *d_b_router, hipStream_t s);
+hipError_t launch_dx_finish(int dtype, const void *dx_in, const float *d_logits, const void *w_router, int64_t n_tok,
+                            int d_model, int n_experts, void *d_x, hipStream_t s);
+size_t conv_bwd_partial_bytes(int64_t B, int64_t L, int d_inner);
+hipError_t launch_conv_backward(int dtype, const void *xz, int64_t ld_xz, const float *conv_w, const float *conv_b,
+                                const void *du_a, const void *du_b, int64_t B, int64_t L, int d_inner, void *d_xpre,
+                                int64_t ld_dx, float *partial, float *d_conv_w, float *d_conv_b, hipStream_t s);
+// dst[m][c][r] = src[m][r][c] for n_mats matrices
+hipError_t launch_transpose(int dtype, const void *src, void *dst, int n_mats, int rows, int cols, hipStream_t s);
+hipError_t launch_pack_dxdbl(int dtype, const float *d_dt_low, const float *d_bc, int64_t n_tok, int dt_rank,
+                             void *d_xdbl, hipStream_t s);
+// C[e][m][n] (f32) = sum over positions p in [offsets[e], offsets[e+1]) of scale[row(p)] * A[row(p)][m] * B[row(p)][n]
+// (rows NULL: row(p) = p; offsets NULL: one group over [0, n_pos); row_scale NULL: 1)
+hipError_t launch_wgrad(int dtype, const void *A, int64_t lda, int M, const void *Bm, int64_t ldb, int N,
+                        const int32_t *rows, const float *row_scale, const int32_t *offsets, int n_groups,
+                        int64_t n_pos, float *C, hipStream_t s);
+
 // timing probes (bench.py --probe): out is f32 scratch of n_blocks * 256 floats
 hipError_t launch_probe_issue(int op, int chains, int n_blocks, int iters, float *out, hipStream_t s);
 hipError_t launch_probe_scan(int parts, int lds, int n_blocks, int tiles, float *out, hipStream_t s);
