@@ -330,6 +330,39 @@ def time_forward(cfg, steps, warmup, with_balance=True):
     return res
 
 
+def backward_rate(cfg, steps, warmup):
+    """rom_layer_backward on the workload (activation recomputation: the call runs the forward pass
+    into its workspace, then the backward pass)."""
+    import numpy as np
+    import torch
+    from paper_2506_18145_amd import RomLayer
+    from rom_synth import make_input, make_weights
+    layer = RomLayer(cfg, make_weights(cfg), device="cuda:0")
+    x = layer.to_device(make_input(cfg))
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(77)
+    d_out = torch.randn(x.shape, generator=g, device="cuda:0").to(x.dtype)
+    for _ in range(warmup):
+        layer.backward(x, d_out)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    evs[0].record()
+    for i in range(steps):
+        d_x, grads = layer.backward(x, d_out)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    ms = _median([evs[i].elapsed_time(evs[i + 1]) for i in range(steps)])
+    n_tok = cfg.batch * cfg.seq_len
+    S = n_tok * cfg.top_k
+    Sx = S if cfg.routed_xdt else n_tok
+    gemm = 2.0 * S * cfg.d_model * 2 * cfg.d_inner + 2.0 * Sx * cfg.d_inner * (cfg.dt_rank + 2 * cfg.d_state) \
+        + 2.0 * Sx * cfg.dt_rank * cfg.d_inner + 2.0 * S * cfg.d_inner * cfg.d_model
+    finite = bool(torch.isfinite(d_x.float()).all().item()) and all(bool(torch.isfinite(v).all().item()) for v in grads.values())
+    return {"workload": f"{cfg.name}: forward recomputation + backward of one layer (top-1), gradients w.r.t. x and all parameters",
+            "ms_per_call": ms, "tokens_per_s": n_tok / (ms * 1e-3),
+            "gemm_tflops_forward_plus_backward": 3.0 * gemm / (ms * 1e-3) / 1e12, "gradients_finite": finite}
+
+
 def config_leg(name, steps, warmup):
     """The same measurement on another of the paper-shaped workloads (beside the headline one)."""
     from rom_synth import get_config
@@ -470,6 +503,7 @@ def main():
     ap.add_argument("--no-shared-xdt", action="store_true",
                     help="skip the extra measurement of the shared x/dt variant of the workload")
     ap.add_argument("--no-ffn", action="store_true", help="skip the extra FFN-MoE layer measurement")
+    ap.add_argument("--no-backward", action="store_true", help="skip the extra backward-pass measurement")
     ap.add_argument("--no-configs", action="store_true", help="skip the legs on the other paper-shaped workloads")
     ap.add_argument("--no-traffic", action="store_true",
                     help="skip the two rocprofv3 counter runs that measure the dominant kernel's HBM traffic")
@@ -564,6 +598,8 @@ def main():
                     "tokens_per_s": n_tok / (rs["ms_median"] * 1e-3),
                     "stages_ms": {k: v["ms"] for k, v in rs["stages"].items()}}
         extra("shared_xdt_variant", shared_leg)
+    if not args.no_backward and cfg.top_k == 1:
+        extra("backward", lambda: backward_rate(cfg, 5, 2))
     if not args.no_ffn:
         extra("ffn_moe", lambda: ffn_moe_rate(cfg, 2 * cfg.d_model, 20, 20))
     if args.hybrid_layers > 0:

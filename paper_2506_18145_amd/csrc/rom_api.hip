@@ -859,7 +859,10 @@ int rom_layer_backward(const rom_dims *d, const rom_weights *w, const void *x, i
   // Eq. (12)/(13): out = gate * (W_out[e] g)
   ROM_TRY(dgrad(d_out, Dm, at(bp.wt_out), E, De, Dm, at(bp.dg_raw), De, 0));           // dg_raw = W_out[e]^T d_out
   ROM_TRY(launch_gate_backward(d->dtype, at(bp.dg_raw), at(p.g), N, De, d_gate, s));
-  ROM_TRY(wgrad(d_out, Dm, Dm, at(p.g), De, De, E, gate, gr->d_w_out));
+  // (the gate weight goes onto d_out once, in the buffer that later receives dx_in, so that the
+  // weight-gradient kernel contracts two plain operands)
+  ROM_TRY(launch_scale_rows(d->dtype, d_out, gate, N, Dm, at(bp.dx_in), s));
+  ROM_TRY(wgrad(at(bp.dx_in), Dm, Dm, at(p.g), De, De, E, nullptr, gr->d_w_out));
   // Eq. (5), (6): scan, gate, softplus
   ROM_TRY(launch_scan_backward(d->dtype, at(p.u), at(p.dt), reinterpret_cast<const float *>(at(p.bc)),
                                at(p.xz) + static_cast<size_t>(De) * eb, 2 * De, at(bp.dg_raw), gate, w->A_log, w->D, B, L,

@@ -26,56 +26,69 @@ __device__ __forceinline__ float sigmoid_f32(float v) { return fast_rcp(1.0f + f
 
 inline dim3 grid1d(int64_t work, int block) { return dim3(static_cast<unsigned>(ceil_div(work, block))); }
 
+// Workgroup barrier for data that travels through LDS only.  __syncthreads() also waits for the
+// wavefront's outstanding global stores (its fence covers global memory), which puts a memory round
+// trip behind every barrier that follows a store; threads of these kernels never read what another
+// thread wrote to global memory, so waiting for the LDS counter is enough.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // ------------------------------------------------------------------ adjoint of the selective scan
 // Same lane = (channel, state) layout as the forward kernel: a 256-thread block owns 16 channels
 // and walks every sequence of the batch, one after the other (the per-channel parameter gradients
 // accumulate in registers in a fixed order).  Per sequence:
 //   pass 1 (forward in time): the state recurrence alone, leaving the state at the start of every
-//           64-step tile in the checkpoint buffer;
-//   pass 2 (backward in time, tile by tile): the tile's states are recomputed from its checkpoint
-//           and kept in registers, then the adjoint recurrence d_h[t-1] = exp(dt_t a) d_h[t] walks
-//           the tile backwards.
+//           16-step group in the checkpoint buffer;
+//   pass 2 (backward in time, 64-step tiles of four groups): a group's states are recomputed from
+//           its checkpoint into registers, then the adjoint recurrence d_h[t-1] = exp(dt_t a) d_h[t]
+//           walks the group backwards.  The group body is unrolled, the loop over groups is not:
+//           unrolled over a whole tile the body outgrew the instruction cache, and a lone wavefront
+//           per SIMD then waited on instruction fetch (6.8 ms instead of 1.5 at 16K steps x 4096 channels).
 // Sums over the 16 states of a channel (d_dt, d_u, y) are DPP row sums; sums over the block's 16
 // channels (d_B, d_C) go through LDS in channel order; the sum of those over the channel groups of
 // the whole layer is left to bwd_reduce_bc_kernel (per-block partial rows in global memory).
-constexpr int kBwdTile = 64, kBwdCh = 16, kBwdPitch = kBwdCh + 1, kBwdGroup = 8;
+constexpr int kBwdTile = 64, kBwdCh = 16, kBwdPitch = kBwdCh + 1, kBwdGroup = 16, kBwdHalf = 8;
 
 struct BwdSmem {
-  float dt[kBwdTile][kBwdPitch], u[kBwdTile][kBwdPitch], z[kBwdTile][kBwdPitch], dg[kBwdTile][kBwdPitch];
+  // per (step, channel), prepared once when the tile is loaded: dt, u, d y = gate * dg * SiLU(z) and
+  // the factor gate * dg * SiLU'(z) of d z
+  float dt[kBwdTile][kBwdPitch], u[kBwdTile][kBwdPitch], dy[kBwdTile][kBwdPitch], dzf[kBwdTile][kBwdPitch];
   float bc[kBwdTile][33];                    // B_0..15, C_0..15 of every step
-  float gate[kBwdTile];
   float o_pre[kBwdTile][kBwdPitch], o_u[kBwdTile][kBwdPitch], o_z[kBwdTile][kBwdPitch];   // outputs of the tile
-  float part_b[kBwdGroup][kBwdCh][17], part_c[kBwdGroup][kBwdCh][17];   // [step in group][channel][state] terms of d_B, d_C
+  float o_bc[kBwdTile][33];                  // this block's share of d_B, d_C of the tile
+  float part_b[kBwdHalf][kBwdCh][17], part_c[kBwdHalf][kBwdCh][17];   // [step in half group][channel][state] terms of d_B, d_C
 };
 
 template <typename T>
 __device__ __forceinline__ void bwd_load_tile(BwdSmem &sm, const T *u_b, const T *dt_b, const T *z_b, int64_t ld_z,
                                               const T *dg_b, const float *bc_b, const float *gate_b, int64_t t0,
                                               int64_t t_end, int d_inner, int tid, bool full) {
-  // thread -> (step row, channel) for the four [64][16] tensors, four rounds
+  // thread -> (step row, channel) for the [64][16] tensors, four rounds
+#pragma unroll
   for (int i = tid; i < kBwdTile * kBwdCh; i += 256) {
     const int row = i / kBwdCh, c = i % kBwdCh;
     const int64_t t = t0 + row;
     const bool ok = t < t_end;
-    sm.dt[row][c] = ok ? to_f32(dt_b[t * d_inner + c]) : 0.0f;
-    sm.u[row][c] = ok ? to_f32(u_b[t * d_inner + c]) : 0.0f;
+    const float dts = ok ? to_f32(dt_b[t * d_inner + c]) : 0.0f;
+    const float us = ok ? to_f32(u_b[t * d_inner + c]) : 0.0f;
+    sm.dt[row][c] = dts;
+    sm.u[row][c] = us;
     if (full) {
-      sm.z[row][c] = ok ? to_f32(z_b[t * ld_z + c]) : 0.0f;
-      sm.dg[row][c] = ok ? to_f32(dg_b[t * d_inner + c]) : 0.0f;
+      const float zs = ok ? to_f32(z_b[t * ld_z + c]) : 0.0f;
+      const float dgs = ok ? to_f32(dg_b[t * d_inner + c]) * (gate_b ? gate_b[t] : 1.0f) : 0.0f;   // gate weight of Eq. (12)
+      const float sig = sigmoid_f32(zs);
+      sm.dy[row][c] = dgs * zs * sig;                                 // g = y * SiLU(z)
+      sm.dzf[row][c] = dgs * sig * (1.0f + zs * (1.0f - sig));
     }
   }
+#pragma unroll
   for (int i = tid; i < kBwdTile * 32; i += 256) {
     const int row = i / 32, c = i % 32;
     const int64_t t = t0 + row;
     sm.bc[row][c] = t < t_end ? bc_b[t * 32 + c] : 0.0f;
   }
-  if (full && tid < kBwdTile) {
-    const int64_t t = t0 + tid;
-    sm.gate[tid] = t < t_end ? (gate_b ? gate_b[t] : 1.0f) : 0.0f;
-  }
 }
 
-// grid: d_inner / 16 blocks.  ckpt: f32 [gridDim.x][n_tiles][16 channels][16 states] (one sequence at a time).
+// grid: d_inner / 16 blocks.  ckpt: f32 [gridDim.x][ceil(L / 16)][16 channels][16 states] (one sequence at a time).
 // d_bc_part: f32 [gridDim.x][N][32].  Outputs d_pre (w.r.t. the softplus argument), d_u, d_z have type T.
 template <typename T>
 __global__ __launch_bounds__(256) void scan_bwd_kernel(
@@ -92,9 +105,10 @@ __global__ __launch_bounds__(256) void scan_bwd_kernel(
   const float a2 = a_nat * 1.44269504088896341f;
   const float d_skip = D[ch];
   const int64_t n_tiles = (L + kBwdTile - 1) / kBwdTile;
-  float *ck = ckpt + static_cast<int64_t>(blockIdx.x) * n_tiles * 256;
+  constexpr int kGroupsPerTile = kBwdTile / kBwdGroup;
+  float *ck = ckpt + static_cast<int64_t>(blockIdx.x) * n_tiles * kGroupsPerTile * 256;
   const int64_t n_tok = n_seq * L;
-  float acc_a = 0.0f, acc_d = 0.0f, acc_bias = 0.0f;       // d_A (this lane's state), d_D, d_dt_bias (all lanes of a row alike)
+  float acc_a = 0.0f, acc_d = 0.0f, acc_bias = 0.0f;       // d_A (this lane's state); d_D, d_dt_bias (alike in the 16 lanes of a channel)
 
   for (int64_t b = 0; b < n_seq; ++b) {
     const T *u_b = u + b * L * d_inner + c0;
@@ -104,82 +118,88 @@ __global__ __launch_bounds__(256) void scan_bwd_kernel(
     const float *bc_b = bc + b * L * 32;
     const float *gate_b = gate ? gate + b * L : nullptr;
 
-    // ---- pass 1: checkpoints
+    // ---- pass 1: the state at the start of every group
     float h = 0.0f;
     for (int64_t ti = 0; ti < n_tiles; ++ti) {
-      ck[ti * 256 + tid] = h;
-      __syncthreads();
+      lds_barrier();
       bwd_load_tile<T>(sm, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ti * kBwdTile, L, d_inner, tid, false);
-      __syncthreads();
-      if (ti + 1 < n_tiles) {          // the last tile's end state is not needed
-#pragma unroll 8
-        for (int s = 0; s < kBwdTile; ++s) {
+      lds_barrier();
+#pragma unroll 1
+      for (int grp = 0; grp < kGroupsPerTile; ++grp) {
+        ck[(ti * kGroupsPerTile + grp) * 256 + tid] = h;
+#pragma unroll
+        for (int j = 0; j < kBwdGroup; ++j) {
+          const int s = grp * kBwdGroup + j;
           const float dts = sm.dt[s][cl];
           h = fmaf(fast_exp2(dts * a2), h, dts * sm.u[s][cl] * sm.bc[s][n]);
         }
       }
     }
 
-    // ---- pass 2: tiles in reverse
+    // ---- pass 2: tiles in reverse, groups in reverse
     float dh = 0.0f;
     for (int64_t ti = n_tiles - 1; ti >= 0; --ti) {
       const int64_t t0 = ti * kBwdTile;
-      __syncthreads();
+      float ck_r[kGroupsPerTile];              // the tile's four checkpoints: one memory round trip, not four
+#pragma unroll
+      for (int grp = 0; grp < kGroupsPerTile; ++grp) ck_r[grp] = ck[(ti * kGroupsPerTile + grp) * 256 + tid];
+      lds_barrier();
       bwd_load_tile<T>(sm, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, t0, L, d_inner, tid, true);
-      __syncthreads();
-      float hs[kBwdTile + 1], da[kBwdTile];
-      hs[0] = ck[ti * 256 + tid];
+      lds_barrier();
 #pragma unroll
-      for (int s = 0; s < kBwdTile; ++s) {
-        const float dts = sm.dt[s][cl];
-        da[s] = fast_exp2(dts * a2);
-        hs[s + 1] = fmaf(da[s], hs[s], dts * sm.u[s][cl] * sm.bc[s][n]);
-      }
+      for (int grp = kGroupsPerTile - 1; grp >= 0; --grp) {
+        float hs[kBwdGroup + 1], da[kBwdGroup], dts[kBwdGroup], dtu[kBwdGroup], bn[kBwdGroup];
+        hs[0] = ck_r[grp];
 #pragma unroll
-      for (int grp = kBwdTile / kBwdGroup - 1; grp >= 0; --grp) {
-#pragma unroll
-        for (int j = kBwdGroup - 1; j >= 0; --j) {
+        for (int j = 0; j < kBwdGroup; ++j) {
           const int s = grp * kBwdGroup + j;
-          const float dts = sm.dt[s][cl], us = sm.u[s][cl], zs = sm.z[s][cl];
-          const float bn = sm.bc[s][n], cn = sm.bc[s][16 + n];
-          const float sig = sigmoid_f32(zs);
-          const float silu_z = zs * sig;
-          const float dgs = sm.dg[s][cl] * sm.gate[s];            // d loss / d g (gate weight of Eq. (12) applied)
-          const float dy = dgs * silu_z;
-          const float y = row_sum16(cn * hs[s + 1]) + d_skip * us;
-          dh = fmaf(cn, dy, dh);                                  // y_t = C_t . h_t
-          const float darg = dh * hs[s] * da[s];                  // d / d (dt_t * A)
-          const float inj = dh * bn;                              // input term dt * B * u
-          const float ddt = row_sum16(fmaf(darg, a_nat, inj * us));
-          const float du = fmaf(row_sum16(inj), dts, d_skip * dy);
-          acc_a = fmaf(darg, dts, acc_a);
-          sm.part_b[j][cl][n] = dh * dts * us;
-          sm.part_c[j][cl][n] = dy * hs[s + 1];
-          dh *= da[s];
-          if (n == 0) {
+          dts[j] = sm.dt[s][cl];
+          dtu[j] = dts[j] * sm.u[s][cl];
+          bn[j] = sm.bc[s][n];
+          da[j] = fast_exp2(dts[j] * a2);
+          hs[j + 1] = fmaf(da[j], hs[j], dtu[j] * bn[j]);
+        }
+#pragma unroll
+        for (int half = 1; half >= 0; --half) {
+#pragma unroll
+          for (int jj = kBwdHalf - 1; jj >= 0; --jj) {
+            const int j = half * kBwdHalf + jj;
+            const int s = grp * kBwdGroup + j;
+            const float us = sm.u[s][cl], cn = sm.bc[s][16 + n], dy = sm.dy[s][cl];
+            const float y = row_sum16(cn * hs[j + 1]) + d_skip * us;
+            dh = fmaf(cn, dy, dh);                                // y_t = C_t . h_t
+            const float darg = dh * hs[j] * da[j];                // d / d (dt_t * A)
+            const float inj = dh * bn[j];                         // input term dt * B * u
+            const float ddt = row_sum16(fmaf(darg, a_nat, inj * us));
+            const float du = fmaf(row_sum16(inj), dts[j], d_skip * dy);
+            acc_a = fmaf(darg, dts[j], acc_a);
+            sm.part_b[jj][cl][n] = dh * dtu[j];
+            sm.part_c[jj][cl][n] = dy * hs[j + 1];
+            dh *= da[j];
+            // (all 16 lanes of the channel hold the same sums and write the same value)
             // dt = softplus(pre): d pre = d dt * sigmoid(pre) = d dt * (1 - exp(-dt))
-            const float dpre = ddt * (1.0f - fast_exp2(-1.44269504088896341f * dts));
+            const float dpre = ddt * (1.0f - fast_exp2(-1.44269504088896341f * dts[j]));
             sm.o_pre[s][cl] = dpre;
             sm.o_u[s][cl] = du;
-            sm.o_z[s][cl] = dgs * y * sig * (1.0f + zs * (1.0f - sig));
+            sm.o_z[s][cl] = sm.dzf[s][cl] * y;
             acc_bias += dpre;
             acc_d = fmaf(dy, us, acc_d);
           }
-        }
-        __syncthreads();
-        // d_B, d_C of this group's steps: sum over the block's channels in channel order
-        {
-          const int j = tid / 32, c = tid % 32;              // 8 steps x 32 values = 256 threads
-          const float(*src)[kBwdCh][17] = c < 16 ? sm.part_b : sm.part_c;
-          float tot = 0.0f;
+          lds_barrier();
+          // d_B, d_C of these eight steps: sum over the block's channels in channel order
+          {
+            const int jj = tid / 32, c = tid % 32;             // 8 steps x 32 values = 256 threads
+            const float(*src)[kBwdCh][17] = c < 16 ? sm.part_b : sm.part_c;
+            float tot = 0.0f;
 #pragma unroll
-          for (int k = 0; k < kBwdCh; ++k) tot += src[j][k][c & 15];
-          const int64_t t = t0 + grp * kBwdGroup + j;
-          if (t < L) d_bc_part[(static_cast<int64_t>(blockIdx.x) * n_tok + b * L + t) * 32 + c] = tot;
+            for (int k = 0; k < kBwdCh; ++k) tot += src[jj][k][c & 15];
+            sm.o_bc[grp * kBwdGroup + half * kBwdHalf + jj][c] = tot;
+          }
+          lds_barrier();
         }
-        __syncthreads();
       }
       // the tile's per-channel outputs
+#pragma unroll
       for (int i = tid; i < kBwdTile * kBwdCh; i += 256) {
         const int row = i / kBwdCh, c = i % kBwdCh;
         const int64_t t = t0 + row;
@@ -189,6 +209,12 @@ __global__ __launch_bounds__(256) void scan_bwd_kernel(
           d_u[at] = from_f32<T>(sm.o_u[row][c]);
           d_z[(b * L + t) * ld_dz + c0 + c] = from_f32<T>(sm.o_z[row][c]);
         }
+      }
+#pragma unroll
+      for (int i = tid; i < kBwdTile * 32; i += 256) {
+        const int row = i / 32, c = i % 32;
+        const int64_t t = t0 + row;
+        if (t < L) d_bc_part[(static_cast<int64_t>(blockIdx.x) * n_tok + b * L + t) * 32 + c] = sm.o_bc[row][c];
       }
     }
   }
@@ -267,36 +293,36 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(const float *__restrict
 // partial[chunk][e][d] = sum over the chunk's tokens of d_logits[n, e] * x[n, d]  (d = d_model is the
 // bias column: x = 1).  grid (ceil((d_model + 1) / 256), n_chunks); a thread owns one column.
 constexpr int kRouterChunk = 512;
-template <typename T>
+template <typename T, int EMAX>
 __global__ __launch_bounds__(256) void router_wgrad_partial_kernel(const float *__restrict__ d_logits,
                                                                    const T *__restrict__ x, int64_t n_tok, int d_model,
                                                                    int n_experts, float *__restrict__ partial) {
-  __shared__ float dl[64][64];                      // [token in round][expert]
+  __shared__ float dl[64][EMAX];                    // [token in round][expert]
   const int d = blockIdx.x * 256 + threadIdx.x;
   const int64_t n0 = static_cast<int64_t>(blockIdx.y) * kRouterChunk;
   const int64_t n1 = n0 + kRouterChunk < n_tok ? n0 + kRouterChunk : n_tok;
-  float acc[64];
+  float acc[EMAX];
 #pragma unroll
-  for (int e = 0; e < 64; ++e) acc[e] = 0.0f;
+  for (int e = 0; e < EMAX; ++e) acc[e] = 0.0f;
   for (int64_t r0 = n0; r0 < n1; r0 += 64) {
     __syncthreads();
-    for (int i = threadIdx.x; i < 64 * n_experts; i += 256) {
-      const int64_t n = r0 + i / n_experts;
-      dl[i / n_experts][i % n_experts] = n < n1 ? d_logits[n * n_experts + i % n_experts] : 0.0f;
+    for (int i = threadIdx.x; i < 64 * EMAX; i += 256) {
+      const int64_t n = r0 + i / EMAX;
+      const int e = i % EMAX;
+      dl[i / EMAX][e] = (n < n1 && e < n_experts) ? d_logits[n * n_experts + e] : 0.0f;
     }
     __syncthreads();
     if (d <= d_model) {
       for (int i = 0; i < 64 && r0 + i < n1; ++i) {
         const float xv = d < d_model ? to_f32(x[(r0 + i) * d_model + d]) : 1.0f;
 #pragma unroll
-        for (int e = 0; e < 64; ++e)
-          if (e < n_experts) acc[e] = fmaf(dl[i][e], xv, acc[e]);
+        for (int e = 0; e < EMAX; ++e) acc[e] = fmaf(dl[i][e], xv, acc[e]);
       }
     }
   }
   if (d <= d_model)
 #pragma unroll
-    for (int e = 0; e < 64; ++e)
+    for (int e = 0; e < EMAX; ++e)
       if (e < n_experts) partial[(static_cast<int64_t>(blockIdx.y) * n_experts + e) * (d_model + 1) + d] = acc[e];
 }
 
@@ -431,12 +457,30 @@ __global__ __launch_bounds__(256) void pack_dxdbl_kernel(const float *__restrict
 // MFMA fragments (eight consecutive positions of one m / n) are read.  fp32 result, fixed order.
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
-constexpr int kWgTile = 128, kWgSlab = 32, kWgPitch = kWgSlab + 8;     // halfs per LDS row (80 bytes: 16-byte aligned rows)
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+constexpr int kWgTile = 128, kWgSlab = 64, kWgPitch = kWgSlab + 8;     // halfs per LDS row (144 bytes: 16-byte aligned rows)
+
+// eight 16-byte pieces (eight consecutive columns of eight consecutive positions) -> for each of the
+// eight columns the eight positions as one 16-byte LDS row segment: word a of column m's segment
+// holds positions 2a, 2a+1, which v_perm_b32 picks out of word m/2 of the two position rows
+__device__ __forceinline__ void wgrad_park8x8(const u32x4_t (&v)[8], bf16_t (*dst)[kWgPitch], int col0, int pos0) {
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {          // word w of a piece = columns 2w, 2w+1
+    u32x4_t lo, hi;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const unsigned int p0 = v[2 * a][w], p1 = v[2 * a + 1][w];
+      lo[a] = __builtin_amdgcn_perm(p1, p0, 0x05040100u);      // (p0.lo16, p1.lo16)
+      hi[a] = __builtin_amdgcn_perm(p1, p0, 0x07060302u);      // (p0.hi16, p1.hi16)
+    }
+    *reinterpret_cast<u32x4_t *>(&dst[col0 + 2 * w][pos0]) = lo;
+    *reinterpret_cast<u32x4_t *>(&dst[col0 + 2 * w + 1][pos0]) = hi;
+  }
+}
 
 __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const bf16_t *__restrict__ A, int64_t lda, int M,
                                                          const bf16_t *__restrict__ Bm, int64_t ldb, int N,
                                                          const int32_t *__restrict__ rows,
-                                                         const float *__restrict__ row_scale,
                                                          const int32_t *__restrict__ offsets, int64_t n_pos,
                                                          float *__restrict__ C) {
   __shared__ __attribute__((aligned(16))) bf16_t As[kWgTile][kWgPitch];
@@ -454,30 +498,28 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const bf16_t *__restric
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
   const int frag_row = lane & 31, frag_half = lane >> 5;
-  // staging: 32 positions x 16 pieces of 8 columns per operand = 512 pieces, two per thread
+  // staging: a slab is 64 positions; threads 0..127 bring the A operand, 128..255 the B operand, each an
+  // 8-position x 8-column block: (position group pg = 0..7, column piece = 0..15)
+  const bool is_a = tid < 128;
+  const int t2 = tid & 127, pg = t2 & 7, piece = t2 >> 3;       // 16 consecutive lanes park into 64 distinct banks
+  const bf16_t *src = is_a ? A : Bm;
+  const int64_t ld = is_a ? lda : ldb;
+  const int col = (is_a ? m0 : n0) + piece * 8;
+  const bool col_ok = col < (is_a ? M : N);
+  bf16_t(*dst)[kWgPitch] = is_a ? As : Bs;
   for (int64_t p0 = p_lo; p0 < p_hi; p0 += kWgSlab) {
-    __syncthreads();
+    u32x4_t v[8];
 #pragma unroll
-    for (int rep = 0; rep < 2; ++rep) {
-      const int q = tid + rep * 256, pp = q / 16, piece = q % 16;
-      const int64_t p = p0 + pp;
-      const bool live = p < p_hi;
-      const int64_t r = live ? (rows ? rows[p] : p) : 0;
-      const float sc = (live && row_scale) ? row_scale[r] : 1.0f;
-      uint4 va = make_uint4(0, 0, 0, 0), vb = make_uint4(0, 0, 0, 0);
-      if (live && m0 + piece * 8 < M) va = *reinterpret_cast<const uint4 *>(A + r * lda + m0 + piece * 8);
-      if (live && n0 + piece * 8 < N) vb = *reinterpret_cast<const uint4 *>(Bm + r * ldb + n0 + piece * 8);
-      const unsigned int *wa = &va.x, *wb = &vb.x;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float lo = __uint_as_float(wa[i] << 16), hi = __uint_as_float(wa[i] & 0xFFFF0000u);
-        if (row_scale) { lo *= sc; hi *= sc; }
-        As[piece * 8 + 2 * i][pp] = f32_to_bf16(lo);
-        As[piece * 8 + 2 * i + 1][pp] = f32_to_bf16(hi);
-        Bs[piece * 8 + 2 * i][pp] = static_cast<bf16_t>(wb[i] & 0xFFFFu);
-        Bs[piece * 8 + 2 * i + 1][pp] = static_cast<bf16_t>(wb[i] >> 16);
+    for (int i = 0; i < 8; ++i) {
+      const int64_t p = p0 + pg * 8 + i;
+      v[i] = u32x4_t{0u, 0u, 0u, 0u};
+      if (p < p_hi && col_ok) {
+        const int64_t r = rows ? rows[p] : p;
+        v[i] = *reinterpret_cast<const u32x4_t *>(src + r * ld + col);
       }
     }
+    __syncthreads();                       // the slab before this one has been multiplied
+    wgrad_park8x8(v, dst, piece * 8, pg * 8);
     __syncthreads();
 #pragma unroll
     for (int kk = 0; kk < kWgSlab / 16; ++kk) {
@@ -504,12 +546,25 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const bf16_t *__restric
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int col = n0 + wn * 64 + j * 32 + q * 8 + frag_half * 4;
+        const int cc = n0 + wn * 64 + j * 32 + q * 8 + frag_half * 4;
+        if (m < M && cc + 3 < N)
+          *reinterpret_cast<float4 *>(Ce + static_cast<int64_t>(m) * N + cc) =
+              make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        else
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (m < M && col + r < N) Ce[static_cast<int64_t>(m) * N + col + r] = acc[i][j][4 * q + r];
+          for (int r = 0; r < 4; ++r)
+            if (m < M && cc + r < N) Ce[static_cast<int64_t>(m) * N + cc + r] = acc[i][j][4 * q + r];
       }
   }
+}
+
+// rows scaled by a per-row factor: dst[n, :] = scale[n] * src[n, :] (the gate weight of Eq. (12) on d_out)
+template <typename T>
+__global__ __launch_bounds__(256) void scale_rows_kernel(const T *__restrict__ src, const float *__restrict__ scale,
+                                                         int64_t n_rows, int n_cols, T *__restrict__ dst) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i >= n_rows * n_cols) return;
+  dst[i] = from_f32<T>(to_f32(src[i]) * scale[i / n_cols]);
 }
 
 // the same contraction on the plain ALUs (fp32, or bf16 shapes the MFMA kernel does not take): 64 x 64 tiles
@@ -566,7 +621,8 @@ __global__ __launch_bounds__(256) void wgrad_simple_kernel(const T *__restrict__
 }  // namespace
 
 size_t scan_bwd_ckpt_bytes(int64_t L, int d_inner) {
-  return static_cast<size_t>(d_inner / kBwdCh) * static_cast<size_t>(ceil_div(L, kBwdTile)) * 256 * sizeof(float);
+  return static_cast<size_t>(d_inner / kBwdCh) * static_cast<size_t>(ceil_div(L, kBwdTile)) * (kBwdTile / kBwdGroup) * 256 *
+         sizeof(float);
 }
 size_t scan_bwd_part_bytes(int64_t n_tok, int d_inner) {
   return static_cast<size_t>(d_inner / kBwdCh) * static_cast<size_t>(n_tok) * 32 * sizeof(float);
@@ -619,12 +675,15 @@ hipError_t launch_router_backward(int dtype, const float *logits, const int32_t 
                      top_k, gate_mode, d_logits);
   const int n_chunks = static_cast<int>(ceil_div(n_tok, kRouterChunk));
   const dim3 grid(static_cast<unsigned>(ceil_div(d_model + 1, 256)), static_cast<unsigned>(n_chunks));
-  if (dtype == ROM_DTYPE_BF16)
-    hipLaunchKernelGGL((router_wgrad_partial_kernel<bf16_t>), grid, dim3(256), 0, s, d_logits,
-                       static_cast<const bf16_t *>(x), n_tok, d_model, n_experts, partial);
-  else
-    hipLaunchKernelGGL((router_wgrad_partial_kernel<float>), grid, dim3(256), 0, s, d_logits,
-                       static_cast<const float *>(x), n_tok, d_model, n_experts, partial);
+#define ROM_RW(T, EMAX)                                                                                       \
+  hipLaunchKernelGGL((router_wgrad_partial_kernel<T, EMAX>), grid, dim3(256), 0, s, d_logits, static_cast<const T *>(x), \
+                     n_tok, d_model, n_experts, partial)
+  if (dtype == ROM_DTYPE_BF16) {
+    if (n_experts <= 8) ROM_RW(bf16_t, 8); else if (n_experts <= 16) ROM_RW(bf16_t, 16); else ROM_RW(bf16_t, 64);
+  } else {
+    if (n_experts <= 8) ROM_RW(float, 8); else if (n_experts <= 16) ROM_RW(float, 16); else ROM_RW(float, 64);
+  }
+#undef ROM_RW
   hipLaunchKernelGGL(router_wgrad_finish_kernel, grid1d(static_cast<int64_t>(n_experts) * (d_model + 1), 256), dim3(256), 0,
                      s, partial, n_chunks, d_model, n_experts, d_w_router, d_b_router);
   return hipGetLastError();
@@ -688,16 +747,28 @@ hipError_t launch_pack_dxdbl(int dtype, const float *d_dt_low, const float *d_bc
   return hipGetLastError();
 }
 
+hipError_t launch_scale_rows(int dtype, const void *src, const float *scale, int64_t n_rows, int n_cols, void *dst,
+                             hipStream_t s) {
+  const dim3 grid = grid1d(n_rows * n_cols, 256);
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL((scale_rows_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(src), scale, n_rows,
+                       n_cols, static_cast<bf16_t *>(dst));
+  else
+    hipLaunchKernelGGL((scale_rows_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(src), scale, n_rows,
+                       n_cols, static_cast<float *>(dst));
+  return hipGetLastError();
+}
+
 hipError_t launch_wgrad(int dtype, const void *A, int64_t lda, int M, const void *Bm, int64_t ldb, int N,
                         const int32_t *rows, const float *row_scale, const int32_t *offsets, int n_groups,
                         int64_t n_pos, float *C, hipStream_t s) {
   const bool mfma = dtype == ROM_DTYPE_BF16 && M % 8 == 0 && N % 8 == 0 && lda % 8 == 0 && ldb % 8 == 0 &&
                     reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(Bm) % 16 == 0;
-  if (mfma) {
+  if (mfma && !row_scale) {
     const dim3 grid(static_cast<unsigned>(ceil_div(N, kWgTile)), static_cast<unsigned>(ceil_div(M, kWgTile)),
                     static_cast<unsigned>(n_groups));
     hipLaunchKernelGGL(wgrad_bf16_kernel, grid, dim3(256), 0, s, static_cast<const bf16_t *>(A), lda, M,
-                       static_cast<const bf16_t *>(Bm), ldb, N, rows, row_scale, offsets, n_pos, C);
+                       static_cast<const bf16_t *>(Bm), ldb, N, rows, offsets, n_pos, C);
     return hipGetLastError();
   }
   const dim3 grid(static_cast<unsigned>(ceil_div(N, 64)), static_cast<unsigned>(ceil_div(M, 64)),

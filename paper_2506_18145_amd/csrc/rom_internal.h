@@ -147,6 +147,8 @@ hipError_t launch_conv_backward(int dtype, const void *xz, int64_t ld_xz, const 
 hipError_t launch_transpose(int dtype, const void *src, void *dst, int n_mats, int rows, int cols, hipStream_t s);
 hipError_t launch_pack_dxdbl(int dtype, const float *d_dt_low, const float *d_bc, int64_t n_tok, int dt_rank,
                              void *d_xdbl, hipStream_t s);
+hipError_t launch_scale_rows(int dtype, const void *src, const float *scale, int64_t n_rows, int n_cols, void *dst,
+                             hipStream_t s);
 // C[e][m][n] (f32) = sum over positions p in [offsets[e], offsets[e+1]) of scale[row(p)] * A[row(p)][m] * B[row(p)][n]
 // (rows NULL: row(p) = p; offsets NULL: one group over [0, n_pos); row_scale NULL: 1)
 hipError_t launch_wgrad(int dtype, const void *A, int64_t lda, int M, const void *Bm, int64_t ldb, int N,
