@@ -427,7 +427,7 @@ BwdPlan make_bwd_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   p.d_pre = take(N * De * b);
   p.d_u_scan = take(N * De * b);
   p.d_xz = take(N * 2 * De * b);
-  p.ckpt = take(scan_bwd_ckpt_bytes(seq_len, d->d_inner));
+  p.ckpt = take(scan_bwd_ckpt_bytes(n_seq, seq_len, d->d_inner));
   p.bc_part = take(scan_bwd_part_bytes(static_cast<int64_t>(N), d->d_inner));
   p.d_bc = take(N * 32 * 4);
   p.d_dt_low = take(N * R * 4);

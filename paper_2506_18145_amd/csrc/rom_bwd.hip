@@ -33,20 +33,56 @@ inline dim3 grid1d(int64_t work, int block) { return dim3(static_cast<unsigned>(
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 // ------------------------------------------------------------------ adjoint of the selective scan
-// Same lane = (channel, state) layout as the forward kernel: a 256-thread block owns 16 channels
-// and walks every sequence of the batch, one after the other (the per-channel parameter gradients
-// accumulate in registers in a fixed order).  Per sequence:
+// Same lane = (channel, state) layout as the forward kernel.  A 256-thread block is one unit of work:
+// 16 channels of one sequence over one chunk of its steps; the grid is (channel blocks, sequences x
+// chunks).  A lone wavefront per SIMD issues an instruction every five clocks at best and hides no
+// LDS latency, so the launcher cuts the sequences into enough chunks for two blocks per CU.  Per unit:
+//   prologue: the state at the chunk's start and the adjoint state flowing in at its end, from the
+//           per-chunk carries (decay product P, end state Q from a zero start, start adjoint R from a
+//           zero end) that scan_bwd_carry_kernel left, combined in chunk order;
 //   pass 1 (forward in time): the state recurrence alone, leaving the state at the start of every
 //           16-step group in the checkpoint buffer;
 //   pass 2 (backward in time, 64-step tiles of four groups): a group's states are recomputed from
 //           its checkpoint into registers, then the adjoint recurrence d_h[t-1] = exp(dt_t a) d_h[t]
-//           walks the group backwards.  The group body is unrolled, the loop over groups is not:
-//           unrolled over a whole tile the body outgrew the instruction cache, and a lone wavefront
-//           per SIMD then waited on instruction fetch (6.8 ms instead of 1.5 at 16K steps x 4096 channels).
+//           walks the group backwards.  The group body is unrolled, the loop over groups is not
+//           (unrolled over a whole tile the body spills registers).
 // Sums over the 16 states of a channel (d_dt, d_u, y) are DPP row sums; sums over the block's 16
 // channels (d_B, d_C) go through LDS in channel order; the sum of those over the channel groups of
-// the whole layer is left to bwd_reduce_bc_kernel (per-block partial rows in global memory).
+// the whole layer is left to bwd_reduce_bc_kernel (per-block partial rows in global memory); the
+// parameter gradients of a unit go to per-unit partials that scan_bwd_finish_kernel sums in unit order.
 constexpr int kBwdTile = 64, kBwdCh = 16, kBwdPitch = kBwdCh + 1, kBwdGroup = 16, kBwdHalf = 8;
+constexpr int kGroupsPerTile = kBwdTile / kBwdGroup;
+
+// Scratch of the adjoint scan, all f32.  Units are numbered (sequence * n_chunks + chunk) * n_cb + channel block.
+struct ScanBwdLayout {
+  int n_cb, n_chunks;
+  int64_t chunk_len;          // steps per chunk, a multiple of the tile
+  int64_t n_units;
+  size_t ckpt, carry_p, carry_q, carry_r, part_a, part_d, part_bias, total;   // offsets in floats
+};
+inline ScanBwdLayout scan_bwd_layout(int64_t B, int64_t L, int d_inner) {
+  ScanBwdLayout l;
+  l.n_cb = d_inner / kBwdCh;
+  const int64_t tiles = ceil_div(L, kBwdTile);
+  int64_t nc = ceil_div(512, static_cast<int64_t>(l.n_cb) * B);       // two blocks for each of the 256 CUs
+  const int64_t max_nc = tiles / 8 > 0 ? tiles / 8 : 1;                 // a chunk is at least 512 steps
+  nc = nc < 1 ? 1 : (nc > max_nc ? max_nc : nc);
+  const int64_t tiles_per_chunk = ceil_div(tiles, nc);
+  l.n_chunks = static_cast<int>(ceil_div(tiles, tiles_per_chunk));
+  l.chunk_len = tiles_per_chunk * kBwdTile;
+  l.n_units = B * l.n_chunks * l.n_cb;
+  size_t off = 0;
+  auto take = [&](size_t n) { size_t o = off; off += (n + 63) / 64 * 64; return o; };
+  l.ckpt = take(static_cast<size_t>(l.n_units) * tiles_per_chunk * kGroupsPerTile * 256);
+  l.carry_p = take(static_cast<size_t>(l.n_units) * 256);
+  l.carry_q = take(static_cast<size_t>(l.n_units) * 256);
+  l.carry_r = take(static_cast<size_t>(l.n_units) * 256);
+  l.part_a = take(static_cast<size_t>(l.n_units) * 256);
+  l.part_d = take(static_cast<size_t>(l.n_units) * kBwdCh);
+  l.part_bias = take(static_cast<size_t>(l.n_units) * kBwdCh);
+  l.total = off;
+  return l;
+}
 
 struct BwdSmem {
   // per (step, channel), prepared once when the tile is loaded: dt, u, d y = gate * dg * SiLU(z) and
@@ -58,170 +94,294 @@ struct BwdSmem {
   float part_b[kBwdHalf][kBwdCh][17], part_c[kBwdHalf][kBwdCh][17];   // [step in half group][channel][state] terms of d_B, d_C
 };
 
+// A tile travels from global memory to LDS in two steps, so that the loads of the next tile are in
+// flight while this one is worked on: bwd_fetch_tile (global -> registers), bwd_park_tile (registers -> LDS).
+struct BwdTileRegs {
+  float dt[4], u[4], z[4], dg[4], bc[8];
+};
+
 template <typename T>
-__device__ __forceinline__ void bwd_load_tile(BwdSmem &sm, const T *u_b, const T *dt_b, const T *z_b, int64_t ld_z,
-                                              const T *dg_b, const float *bc_b, const float *gate_b, int64_t t0,
-                                              int64_t t_end, int d_inner, int tid, bool full) {
+__device__ __forceinline__ void bwd_fetch_tile(BwdTileRegs &r, const T *u_b, const T *dt_b, const T *z_b, int64_t ld_z,
+                                               const T *dg_b, const float *bc_b, const float *gate_b, int64_t t0,
+                                               int64_t t_end, int d_inner, int tid, bool full) {
   // thread -> (step row, channel) for the [64][16] tensors, four rounds
 #pragma unroll
-  for (int i = tid; i < kBwdTile * kBwdCh; i += 256) {
+  for (int q = 0; q < 4; ++q) {
+    const int i = tid + q * 256;
     const int row = i / kBwdCh, c = i % kBwdCh;
     const int64_t t = t0 + row;
     const bool ok = t < t_end;
-    const float dts = ok ? to_f32(dt_b[t * d_inner + c]) : 0.0f;
-    const float us = ok ? to_f32(u_b[t * d_inner + c]) : 0.0f;
-    sm.dt[row][c] = dts;
-    sm.u[row][c] = us;
+    r.dt[q] = ok ? to_f32(dt_b[t * d_inner + c]) : 0.0f;
+    r.u[q] = ok ? to_f32(u_b[t * d_inner + c]) : 0.0f;
     if (full) {
-      const float zs = ok ? to_f32(z_b[t * ld_z + c]) : 0.0f;
-      const float dgs = ok ? to_f32(dg_b[t * d_inner + c]) * (gate_b ? gate_b[t] : 1.0f) : 0.0f;   // gate weight of Eq. (12)
+      r.z[q] = ok ? to_f32(z_b[t * ld_z + c]) : 0.0f;
+      r.dg[q] = ok ? to_f32(dg_b[t * d_inner + c]) * (gate_b ? gate_b[t] : 1.0f) : 0.0f;   // gate weight of Eq. (12)
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const int i = tid + q * 256;
+    const int64_t t = t0 + i / 32;
+    r.bc[q] = t < t_end ? bc_b[t * 32 + i % 32] : 0.0f;
+  }
+}
+
+__device__ __forceinline__ void bwd_park_tile(BwdSmem &sm, const BwdTileRegs &r, int tid, bool full) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int i = tid + q * 256;
+    const int row = i / kBwdCh, c = i % kBwdCh;
+    sm.dt[row][c] = r.dt[q];
+    sm.u[row][c] = r.u[q];
+    if (full) {
+      const float zs = r.z[q], dgs = r.dg[q];
       const float sig = sigmoid_f32(zs);
       sm.dy[row][c] = dgs * zs * sig;                                 // g = y * SiLU(z)
       sm.dzf[row][c] = dgs * sig * (1.0f + zs * (1.0f - sig));
     }
   }
 #pragma unroll
-  for (int i = tid; i < kBwdTile * 32; i += 256) {
-    const int row = i / 32, c = i % 32;
-    const int64_t t = t0 + row;
-    sm.bc[row][c] = t < t_end ? bc_b[t * 32 + c] : 0.0f;
+  for (int q = 0; q < 8; ++q) {
+    const int i = tid + q * 256;
+    sm.bc[i / 32][i % 32] = r.bc[q];
   }
 }
 
-// grid: d_inner / 16 blocks.  ckpt: f32 [gridDim.x][ceil(L / 16)][16 channels][16 states] (one sequence at a time).
-// d_bc_part: f32 [gridDim.x][N][32].  Outputs d_pre (w.r.t. the softplus argument), d_u, d_z have type T.
+// Carries of one chunk (only launched when the sequences are cut into chunks): grid (n_cb, B * n_chunks).
+//   P = prod_t exp(dt_t a)                       decay over the chunk
+//   Q = state at the chunk's end from a zero state at its start
+//   R = adjoint state leaving the chunk's start from a zero adjoint state at its end
 template <typename T>
-__global__ __launch_bounds__(256) void scan_bwd_kernel(
+__global__ __launch_bounds__(256) void scan_bwd_carry_kernel(
     const T *__restrict__ u, const T *__restrict__ dt, const float *__restrict__ bc, const T *__restrict__ z,
-    int64_t ld_z, const T *__restrict__ dg, const float *__restrict__ gate, const float *__restrict__ A_log,
-    const float *__restrict__ D, int64_t n_seq, int64_t L, int d_inner, float *__restrict__ ckpt,
-    T *__restrict__ d_pre, T *__restrict__ d_u, T *__restrict__ d_z, int64_t ld_dz, float *__restrict__ d_bc_part,
-    float *__restrict__ d_A_log, float *__restrict__ d_D, float *__restrict__ d_dt_bias) {
+    int64_t ld_z, const T *__restrict__ dg, const float *__restrict__ gate, const float *__restrict__ A_log, int64_t L,
+    int d_inner, int n_chunks, int64_t chunk_len, float *__restrict__ carry_p, float *__restrict__ carry_q,
+    float *__restrict__ carry_r) {
   __shared__ BwdSmem sm;
   const int tid = threadIdx.x;
   const int n = tid & 15, cl = tid >> 4;
   const int c0 = blockIdx.x * kBwdCh, ch = c0 + cl;
+  const int64_t b = blockIdx.y / n_chunks, k = blockIdx.y % n_chunks;
+  const int64_t ts = k * chunk_len, te = ts + chunk_len < L ? ts + chunk_len : L;
+  const int64_t n_tiles = (te - ts + kBwdTile - 1) / kBwdTile;
+  const float a2 = -__expf(A_log[static_cast<int64_t>(ch) * 16 + n]) * 1.44269504088896341f;
+  const T *u_b = u + b * L * d_inner + c0;
+  const T *dt_b = dt + b * L * d_inner + c0;
+  const T *z_b = z + b * L * ld_z + c0;
+  const T *dg_b = dg + b * L * d_inner + c0;
+  const float *bc_b = bc + b * L * 32;
+  const float *gate_b = gate ? gate + b * L : nullptr;
+
+  BwdTileRegs regs;
+  float h = 0.0f, sum_dt = 0.0f;
+  bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts, te, d_inner, tid, false);
+  for (int64_t ti = 0; ti < n_tiles; ++ti) {
+    lds_barrier();
+    bwd_park_tile(sm, regs, tid, false);
+    lds_barrier();
+    if (ti + 1 < n_tiles)
+      bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + (ti + 1) * kBwdTile, te, d_inner, tid, false);
+    else
+      bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + ti * kBwdTile, te, d_inner, tid, true);
+#pragma unroll 16
+    for (int s2 = 0; s2 < kBwdTile; ++s2) {
+      const float dts = sm.dt[s2][cl];
+      sum_dt += dts;
+      h = fmaf(fast_exp2(dts * a2), h, dts * sm.u[s2][cl] * sm.bc[s2][n]);
+    }
+  }
+  float gq = 0.0f;
+  for (int64_t ti = n_tiles - 1; ti >= 0; --ti) {
+    lds_barrier();
+    bwd_park_tile(sm, regs, tid, true);
+    lds_barrier();
+    if (ti > 0)
+      bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + (ti - 1) * kBwdTile, te, d_inner, tid, true);
+#pragma unroll 16
+    for (int s2 = kBwdTile - 1; s2 >= 0; --s2)
+      gq = fmaf(sm.bc[s2][16 + n], sm.dy[s2][cl], gq) * fast_exp2(sm.dt[s2][cl] * a2);
+  }
+  const int64_t unit = (static_cast<int64_t>(blockIdx.y)) * gridDim.x + blockIdx.x;
+  carry_p[unit * 256 + tid] = fast_exp2(sum_dt * a2);
+  carry_q[unit * 256 + tid] = h;
+  carry_r[unit * 256 + tid] = gq;
+}
+
+// grid (n_cb, B * n_chunks).  ckpt: f32 [unit][groups of the chunk][16 channels][16 states].
+// d_bc_part: f32 [n_cb][N][32].  Outputs d_pre (w.r.t. the softplus argument), d_u, d_z have type T.
+template <typename T>
+__global__ __launch_bounds__(256) void scan_bwd_kernel(
+    const T *__restrict__ u, const T *__restrict__ dt, const float *__restrict__ bc, const T *__restrict__ z,
+    int64_t ld_z, const T *__restrict__ dg, const float *__restrict__ gate, const float *__restrict__ A_log,
+    const float *__restrict__ D, int64_t n_seq, int64_t L, int d_inner, int n_chunks, int64_t chunk_len,
+    float *__restrict__ ckpt, const float *__restrict__ carry_p, const float *__restrict__ carry_q,
+    const float *__restrict__ carry_r, T *__restrict__ d_pre, T *__restrict__ d_u, T *__restrict__ d_z, int64_t ld_dz,
+    float *__restrict__ d_bc_part, float *__restrict__ part_a, float *__restrict__ part_d,
+    float *__restrict__ part_bias) {
+  __shared__ BwdSmem sm;
+  const int tid = threadIdx.x;
+  const int n = tid & 15, cl = tid >> 4;
+  const int c0 = blockIdx.x * kBwdCh, ch = c0 + cl;
+  const int64_t b = blockIdx.y / n_chunks, k = blockIdx.y % n_chunks;
+  const int64_t ts = k * chunk_len, te = ts + chunk_len < L ? ts + chunk_len : L;
+  const int64_t n_tiles = (te - ts + kBwdTile - 1) / kBwdTile;
+  const int64_t unit = static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x;
   const float a_nat = -__expf(A_log[static_cast<int64_t>(ch) * 16 + n]);      // A = -exp(A_log)
   const float a2 = a_nat * 1.44269504088896341f;
   const float d_skip = D[ch];
-  const int64_t n_tiles = (L + kBwdTile - 1) / kBwdTile;
-  constexpr int kGroupsPerTile = kBwdTile / kBwdGroup;
-  float *ck = ckpt + static_cast<int64_t>(blockIdx.x) * n_tiles * kGroupsPerTile * 256;
+  float *ck = ckpt + unit * (chunk_len / kBwdGroup) * 256;
   const int64_t n_tok = n_seq * L;
   float acc_a = 0.0f, acc_d = 0.0f, acc_bias = 0.0f;       // d_A (this lane's state); d_D, d_dt_bias (alike in the 16 lanes of a channel)
 
-  for (int64_t b = 0; b < n_seq; ++b) {
-    const T *u_b = u + b * L * d_inner + c0;
-    const T *dt_b = dt + b * L * d_inner + c0;
-    const T *z_b = z + b * L * ld_z + c0;
-    const T *dg_b = dg + b * L * d_inner + c0;
-    const float *bc_b = bc + b * L * 32;
-    const float *gate_b = gate ? gate + b * L : nullptr;
+  const T *u_b = u + b * L * d_inner + c0;
+  const T *dt_b = dt + b * L * d_inner + c0;
+  const T *z_b = z + b * L * ld_z + c0;
+  const T *dg_b = dg + b * L * d_inner + c0;
+  const float *bc_b = bc + b * L * 32;
+  const float *gate_b = gate ? gate + b * L : nullptr;
 
-    // ---- pass 1: the state at the start of every group
-    float h = 0.0f;
-    for (int64_t ti = 0; ti < n_tiles; ++ti) {
-      lds_barrier();
-      bwd_load_tile<T>(sm, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ti * kBwdTile, L, d_inner, tid, false);
-      lds_barrier();
-#pragma unroll 1
-      for (int grp = 0; grp < kGroupsPerTile; ++grp) {
-        ck[(ti * kGroupsPerTile + grp) * 256 + tid] = h;
-#pragma unroll
-        for (int j = 0; j < kBwdGroup; ++j) {
-          const int s = grp * kBwdGroup + j;
-          const float dts = sm.dt[s][cl];
-          h = fmaf(fast_exp2(dts * a2), h, dts * sm.u[s][cl] * sm.bc[s][n]);
-        }
-      }
+  // ---- prologue: the carries of the chunks before (state) and after (adjoint state) this one
+  float h = 0.0f, dh = 0.0f;
+  if (n_chunks > 1) {
+    const int64_t unit0 = b * n_chunks * gridDim.x + blockIdx.x;      // chunk 0 of this sequence and channel block
+    for (int64_t j = 0; j < k; ++j) {
+      const int64_t at = (unit0 + j * gridDim.x) * 256 + tid;
+      h = fmaf(carry_p[at], h, carry_q[at]);
     }
+    for (int64_t j = n_chunks - 1; j > k; --j) {
+      const int64_t at = (unit0 + j * gridDim.x) * 256 + tid;
+      dh = fmaf(carry_p[at], dh, carry_r[at]);
+    }
+  }
 
-    // ---- pass 2: tiles in reverse, groups in reverse
-    float dh = 0.0f;
-    for (int64_t ti = n_tiles - 1; ti >= 0; --ti) {
-      const int64_t t0 = ti * kBwdTile;
-      float ck_r[kGroupsPerTile];              // the tile's four checkpoints: one memory round trip, not four
+  // ---- pass 1: the state at the start of every group
+  BwdTileRegs regs;
+  bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts, te, d_inner, tid, false);
+  for (int64_t ti = 0; ti < n_tiles; ++ti) {
+    lds_barrier();
+    bwd_park_tile(sm, regs, tid, false);
+    lds_barrier();
+    if (ti + 1 < n_tiles)      // the next tile; after the last one, the same tile again with the factors pass 2 needs
+      bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + (ti + 1) * kBwdTile, te, d_inner, tid, false);
+    else
+      bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + ti * kBwdTile, te, d_inner, tid, true);
+#pragma unroll 1
+    for (int grp = 0; grp < kGroupsPerTile; ++grp) {
+      ck[(ti * kGroupsPerTile + grp) * 256 + tid] = h;
 #pragma unroll
-      for (int grp = 0; grp < kGroupsPerTile; ++grp) ck_r[grp] = ck[(ti * kGroupsPerTile + grp) * 256 + tid];
-      lds_barrier();
-      bwd_load_tile<T>(sm, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, t0, L, d_inner, tid, true);
-      lds_barrier();
-#pragma unroll
-      for (int grp = kGroupsPerTile - 1; grp >= 0; --grp) {
-        float hs[kBwdGroup + 1], da[kBwdGroup], dts[kBwdGroup], dtu[kBwdGroup], bn[kBwdGroup];
-        hs[0] = ck_r[grp];
-#pragma unroll
-        for (int j = 0; j < kBwdGroup; ++j) {
-          const int s = grp * kBwdGroup + j;
-          dts[j] = sm.dt[s][cl];
-          dtu[j] = dts[j] * sm.u[s][cl];
-          bn[j] = sm.bc[s][n];
-          da[j] = fast_exp2(dts[j] * a2);
-          hs[j + 1] = fmaf(da[j], hs[j], dtu[j] * bn[j]);
-        }
-#pragma unroll
-        for (int half = 1; half >= 0; --half) {
-#pragma unroll
-          for (int jj = kBwdHalf - 1; jj >= 0; --jj) {
-            const int j = half * kBwdHalf + jj;
-            const int s = grp * kBwdGroup + j;
-            const float us = sm.u[s][cl], cn = sm.bc[s][16 + n], dy = sm.dy[s][cl];
-            const float y = row_sum16(cn * hs[j + 1]) + d_skip * us;
-            dh = fmaf(cn, dy, dh);                                // y_t = C_t . h_t
-            const float darg = dh * hs[j] * da[j];                // d / d (dt_t * A)
-            const float inj = dh * bn[j];                         // input term dt * B * u
-            const float ddt = row_sum16(fmaf(darg, a_nat, inj * us));
-            const float du = fmaf(row_sum16(inj), dts[j], d_skip * dy);
-            acc_a = fmaf(darg, dts[j], acc_a);
-            sm.part_b[jj][cl][n] = dh * dtu[j];
-            sm.part_c[jj][cl][n] = dy * hs[j + 1];
-            dh *= da[j];
-            // (all 16 lanes of the channel hold the same sums and write the same value)
-            // dt = softplus(pre): d pre = d dt * sigmoid(pre) = d dt * (1 - exp(-dt))
-            const float dpre = ddt * (1.0f - fast_exp2(-1.44269504088896341f * dts[j]));
-            sm.o_pre[s][cl] = dpre;
-            sm.o_u[s][cl] = du;
-            sm.o_z[s][cl] = sm.dzf[s][cl] * y;
-            acc_bias += dpre;
-            acc_d = fmaf(dy, us, acc_d);
-          }
-          lds_barrier();
-          // d_B, d_C of these eight steps: sum over the block's channels in channel order
-          {
-            const int jj = tid / 32, c = tid % 32;             // 8 steps x 32 values = 256 threads
-            const float(*src)[kBwdCh][17] = c < 16 ? sm.part_b : sm.part_c;
-            float tot = 0.0f;
-#pragma unroll
-            for (int k = 0; k < kBwdCh; ++k) tot += src[jj][k][c & 15];
-            sm.o_bc[grp * kBwdGroup + half * kBwdHalf + jj][c] = tot;
-          }
-          lds_barrier();
-        }
-      }
-      // the tile's per-channel outputs
-#pragma unroll
-      for (int i = tid; i < kBwdTile * kBwdCh; i += 256) {
-        const int row = i / kBwdCh, c = i % kBwdCh;
-        const int64_t t = t0 + row;
-        if (t < L) {
-          const int64_t at = (b * L + t) * d_inner + c0 + c;
-          d_pre[at] = from_f32<T>(sm.o_pre[row][c]);
-          d_u[at] = from_f32<T>(sm.o_u[row][c]);
-          d_z[(b * L + t) * ld_dz + c0 + c] = from_f32<T>(sm.o_z[row][c]);
-        }
-      }
-#pragma unroll
-      for (int i = tid; i < kBwdTile * 32; i += 256) {
-        const int row = i / 32, c = i % 32;
-        const int64_t t = t0 + row;
-        if (t < L) d_bc_part[(static_cast<int64_t>(blockIdx.x) * n_tok + b * L + t) * 32 + c] = sm.o_bc[row][c];
+      for (int j = 0; j < kBwdGroup; ++j) {
+        const int s2 = grp * kBwdGroup + j;
+        const float dts = sm.dt[s2][cl];
+        h = fmaf(fast_exp2(dts * a2), h, dts * sm.u[s2][cl] * sm.bc[s2][n]);
       }
     }
   }
-  d_A_log[static_cast<int64_t>(ch) * 16 + n] = acc_a * a_nat;      // d A_log = d A * A
+
+  // ---- pass 2: tiles in reverse, groups in reverse
+  for (int64_t ti = n_tiles - 1; ti >= 0; --ti) {
+    const int64_t t0 = ts + ti * kBwdTile;
+    // the checkpoint of a group is fetched one group ahead of its use
+    float ck_next = ck[(ti * kGroupsPerTile + kGroupsPerTile - 1) * 256 + tid];
+    lds_barrier();
+    bwd_park_tile(sm, regs, tid, true);
+    lds_barrier();
+    if (ti > 0)
+      bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, t0 - kBwdTile, te, d_inner, tid, true);
+#pragma unroll 1
+    for (int grp = kGroupsPerTile - 1; grp >= 0; --grp) {
+      float hs[kBwdGroup + 1], da[kBwdGroup], dts[kBwdGroup], dtu[kBwdGroup], bn[kBwdGroup];
+      hs[0] = ck_next;
+      if (grp > 0) ck_next = ck[(ti * kGroupsPerTile + grp - 1) * 256 + tid];
+#pragma unroll
+      for (int j = 0; j < kBwdGroup; ++j) {
+        const int s2 = grp * kBwdGroup + j;
+        dts[j] = sm.dt[s2][cl];
+        dtu[j] = dts[j] * sm.u[s2][cl];
+        bn[j] = sm.bc[s2][n];
+        da[j] = fast_exp2(dts[j] * a2);
+        hs[j + 1] = fmaf(da[j], hs[j], dtu[j] * bn[j]);
+      }
+#pragma unroll
+      for (int half = 1; half >= 0; --half) {
+#pragma unroll
+        for (int jj = kBwdHalf - 1; jj >= 0; --jj) {
+          const int j = half * kBwdHalf + jj;
+          const int s2 = grp * kBwdGroup + j;
+          const float us = sm.u[s2][cl], cn = sm.bc[s2][16 + n], dy = sm.dy[s2][cl];
+          const float y = row_sum16(cn * hs[j + 1]) + d_skip * us;
+          dh = fmaf(cn, dy, dh);                                // y_t = C_t . h_t
+          const float darg = dh * hs[j] * da[j];                // d / d (dt_t * A)
+          const float inj = dh * bn[j];                         // input term dt * B * u
+          const float ddt = row_sum16(fmaf(darg, a_nat, inj * us));
+          const float du = fmaf(row_sum16(inj), dts[j], d_skip * dy);
+          acc_a = fmaf(darg, dts[j], acc_a);
+          sm.part_b[jj][cl][n] = dh * dtu[j];
+          sm.part_c[jj][cl][n] = dy * hs[j + 1];
+          dh *= da[j];
+          // (all 16 lanes of the channel hold the same sums and write the same value)
+          // dt = softplus(pre): d pre = d dt * sigmoid(pre) = d dt * (1 - exp(-dt))
+          const float dpre = ddt * (1.0f - fast_exp2(-1.44269504088896341f * dts[j]));
+          sm.o_pre[s2][cl] = dpre;
+          sm.o_u[s2][cl] = du;
+          sm.o_z[s2][cl] = sm.dzf[s2][cl] * y;
+          acc_bias += dpre;
+          acc_d = fmaf(dy, us, acc_d);
+        }
+        lds_barrier();
+        // d_B, d_C of these eight steps: sum over the block's channels in channel order
+        {
+          const int jj = tid / 32, c = tid % 32;             // 8 steps x 32 values = 256 threads
+          const float(*src)[kBwdCh][17] = c < 16 ? sm.part_b : sm.part_c;
+          float tot = 0.0f;
+#pragma unroll
+          for (int q = 0; q < kBwdCh; ++q) tot += src[jj][q][c & 15];
+          sm.o_bc[grp * kBwdGroup + half * kBwdHalf + jj][c] = tot;
+        }
+        lds_barrier();
+      }
+    }
+    // the tile's per-channel outputs
+#pragma unroll
+    for (int i = tid; i < kBwdTile * kBwdCh; i += 256) {
+      const int row = i / kBwdCh, c = i % kBwdCh;
+      const int64_t t = t0 + row;
+      if (t < te) {
+        const int64_t at = (b * L + t) * d_inner + c0 + c;
+        d_pre[at] = from_f32<T>(sm.o_pre[row][c]);
+        d_u[at] = from_f32<T>(sm.o_u[row][c]);
+        d_z[(b * L + t) * ld_dz + c0 + c] = from_f32<T>(sm.o_z[row][c]);
+      }
+    }
+#pragma unroll
+    for (int i = tid; i < kBwdTile * 32; i += 256) {
+      const int row = i / 32, c = i % 32;
+      const int64_t t = t0 + row;
+      if (t < te) d_bc_part[(static_cast<int64_t>(blockIdx.x) * n_tok + b * L + t) * 32 + c] = sm.o_bc[row][c];
+    }
+  }
+  part_a[unit * 256 + tid] = acc_a * a_nat;                            // d A_log = d A * A
   if (n == 0) {
-    d_D[ch] = acc_d;
-    d_dt_bias[ch] = acc_bias;
+    part_d[unit * kBwdCh + cl] = acc_d;
+    part_bias[unit * kBwdCh + cl] = acc_bias;
+  }
+}
+
+// d_A_log, d_D, d_dt_bias: the units' partials summed in unit order.  One thread per (channel, state).
+__global__ __launch_bounds__(256) void scan_bwd_finish_kernel(const float *__restrict__ part_a,
+                                                              const float *__restrict__ part_d,
+                                                              const float *__restrict__ part_bias, int n_cb,
+                                                              int64_t n_rep, float *__restrict__ d_A_log,
+                                                              float *__restrict__ d_D, float *__restrict__ d_dt_bias) {
+  const int cb = blockIdx.x, tid = threadIdx.x;
+  float a = 0.0f;
+  for (int64_t r = 0; r < n_rep; ++r) a += part_a[(r * n_cb + cb) * 256 + tid];
+  d_A_log[static_cast<int64_t>(cb) * 256 + tid] = a;
+  if (tid < 2 * kBwdCh) {
+    const float *src = tid < kBwdCh ? part_d : part_bias;
+    const int c = tid % kBwdCh;
+    float v = 0.0f;
+    for (int64_t r = 0; r < n_rep; ++r) v += src[(r * n_cb + cb) * kBwdCh + c];
+    (tid < kBwdCh ? d_D : d_dt_bias)[cb * kBwdCh + c] = v;
   }
 }
 
@@ -620,12 +780,38 @@ __global__ __launch_bounds__(256) void wgrad_simple_kernel(const T *__restrict__
 
 }  // namespace
 
-size_t scan_bwd_ckpt_bytes(int64_t L, int d_inner) {
-  return static_cast<size_t>(d_inner / kBwdCh) * static_cast<size_t>(ceil_div(L, kBwdTile)) * (kBwdTile / kBwdGroup) * 256 *
-         sizeof(float);
+size_t scan_bwd_ckpt_bytes(int64_t B, int64_t L, int d_inner) {
+  return scan_bwd_layout(B, L, d_inner).total * sizeof(float);
 }
 size_t scan_bwd_part_bytes(int64_t n_tok, int d_inner) {
   return static_cast<size_t>(d_inner / kBwdCh) * static_cast<size_t>(n_tok) * 32 * sizeof(float);
+}
+
+template <typename T>
+static hipError_t launch_scan_backward_t(const void *u, const void *dt, const float *bc, const void *z, int64_t ld_z,
+                                         const void *dg, const float *gate, const float *A_log, const float *D, int64_t B,
+                                         int64_t L, int d_inner, float *ws, float *d_bc_part, void *d_pre, void *d_u,
+                                         void *d_z, int64_t ld_dz, float *d_A_log, float *d_D, float *d_dt_bias,
+                                         hipStream_t s) {
+  const ScanBwdLayout l = scan_bwd_layout(B, L, d_inner);
+  const dim3 grid(static_cast<unsigned>(l.n_cb), static_cast<unsigned>(B * l.n_chunks));
+  if (l.n_chunks > 1) {
+    hipLaunchKernelGGL((scan_bwd_carry_kernel<T>), grid, dim3(256), 0, s, static_cast<const T *>(u),
+                       static_cast<const T *>(dt), bc, static_cast<const T *>(z), ld_z, static_cast<const T *>(dg), gate,
+                       A_log, L, d_inner, l.n_chunks, l.chunk_len, ws + l.carry_p, ws + l.carry_q, ws + l.carry_r);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((scan_bwd_kernel<T>), grid, dim3(256), 0, s, static_cast<const T *>(u), static_cast<const T *>(dt),
+                     bc, static_cast<const T *>(z), ld_z, static_cast<const T *>(dg), gate, A_log, D, B, L, d_inner,
+                     l.n_chunks, l.chunk_len, ws + l.ckpt, ws + l.carry_p, ws + l.carry_q, ws + l.carry_r,
+                     static_cast<T *>(d_pre), static_cast<T *>(d_u), static_cast<T *>(d_z), ld_dz, d_bc_part,
+                     ws + l.part_a, ws + l.part_d, ws + l.part_bias);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(scan_bwd_finish_kernel, dim3(static_cast<unsigned>(l.n_cb)), dim3(256), 0, s, ws + l.part_a,
+                     ws + l.part_d, ws + l.part_bias, l.n_cb, B * l.n_chunks, d_A_log, d_D, d_dt_bias);
+  return hipGetLastError();
 }
 
 hipError_t launch_scan_backward(int dtype, const void *u, const void *dt, const float *bc, const void *z, int64_t ld_z,
@@ -633,18 +819,12 @@ hipError_t launch_scan_backward(int dtype, const void *u, const void *dt, const 
                                 int64_t L, int d_inner, float *ckpt, float *d_bc_part, void *d_pre, void *d_u, void *d_z,
                                 int64_t ld_dz, float *d_bc, float *d_A_log, float *d_D, float *d_dt_bias,
                                 hipStream_t s) {
-  const dim3 grid(static_cast<unsigned>(d_inner / kBwdCh));
-  if (dtype == ROM_DTYPE_BF16)
-    hipLaunchKernelGGL((scan_bwd_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(u),
-                       static_cast<const bf16_t *>(dt), bc, static_cast<const bf16_t *>(z), ld_z,
-                       static_cast<const bf16_t *>(dg), gate, A_log, D, B, L, d_inner, ckpt, static_cast<bf16_t *>(d_pre),
-                       static_cast<bf16_t *>(d_u), static_cast<bf16_t *>(d_z), ld_dz, d_bc_part, d_A_log, d_D, d_dt_bias);
-  else
-    hipLaunchKernelGGL((scan_bwd_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(u),
-                       static_cast<const float *>(dt), bc, static_cast<const float *>(z), ld_z,
-                       static_cast<const float *>(dg), gate, A_log, D, B, L, d_inner, ckpt, static_cast<float *>(d_pre),
-                       static_cast<float *>(d_u), static_cast<float *>(d_z), ld_dz, d_bc_part, d_A_log, d_D, d_dt_bias);
-  hipError_t e = hipGetLastError();
+  if (B * scan_bwd_layout(B, L, d_inner).n_chunks > 65535) return hipErrorInvalidValue;
+  hipError_t e = dtype == ROM_DTYPE_BF16
+                     ? launch_scan_backward_t<bf16_t>(u, dt, bc, z, ld_z, dg, gate, A_log, D, B, L, d_inner, ckpt, d_bc_part,
+                                                      d_pre, d_u, d_z, ld_dz, d_A_log, d_D, d_dt_bias, s)
+                     : launch_scan_backward_t<float>(u, dt, bc, z, ld_z, dg, gate, A_log, D, B, L, d_inner, ckpt, d_bc_part,
+                                                     d_pre, d_u, d_z, ld_dz, d_A_log, d_D, d_dt_bias, s);
   if (e != hipSuccess) return e;
   const int64_t n_tok = B * L;
   hipLaunchKernelGGL(bwd_reduce_bc_kernel, grid1d(n_tok * 32, 256), dim3(256), 0, s, d_bc_part, d_inner / kBwdCh, n_tok,

@@ -121,7 +121,8 @@ hipError_t launch_combine(int dtype, const void *op, const int32_t *inv_perm, co
                           hipStream_t s);
 
 // ---------------------------------------------------------------- backward pass (rom_bwd.hip)
-size_t scan_bwd_ckpt_bytes(int64_t L, int d_inner);
+// scratch of the adjoint scan: state checkpoints, chunk carries and per-unit parameter-gradient partials
+size_t scan_bwd_ckpt_bytes(int64_t B, int64_t L, int d_inner);
 size_t scan_bwd_part_bytes(int64_t n_tok, int d_inner);
 // adjoint of scan + gate + softplus: dg is d loss / d (W_out^T d_out) per token, gate (f32 [N] or NULL = 1) the
 // weight it is multiplied by; writes d_pre (w.r.t. the softplus argument), d_u (scan part), d_z (pitch ld_dz), all of
