@@ -371,6 +371,10 @@ ROM_API const char *rom_strerror(int code);
 #define ROM_STAGE_COMBINE   8  /* un-permute + gate-weighted sum, Eq. (12) (K > 1)     */
 #define ROM_STAGE_COUNT     9
 ROM_API int rom_profile_enable(int max_calls);
+/* Restricts the timing to the stages whose bit (1u << ROM_STAGE_*) is set; the default is all.  An
+ * event between two kernels costs several microseconds of launch overlap, so a benchmark that
+ * wants one kernel's duration inside an otherwise undisturbed call selects that stage alone. */
+ROM_API int rom_profile_select(unsigned stage_mask);
 ROM_API int rom_profile_collect(double *stage_ms, int *n_calls);
 /* The same per call: stage_ms (host) [max_calls][ROM_STAGE_COUNT] receives the milliseconds of
  * every stage of each of the first max_calls recorded calls (0 for a stage that did not run). */

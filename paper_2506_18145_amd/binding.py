@@ -114,6 +114,8 @@ def load_library() -> ctypes.CDLL:
     lib.rom_strerror.argtypes = [ctypes.c_int]
     lib.rom_profile_enable.restype = ctypes.c_int
     lib.rom_profile_enable.argtypes = [ctypes.c_int]
+    lib.rom_profile_select.restype = ctypes.c_int
+    lib.rom_profile_select.argtypes = [ctypes.c_uint]
     lib.rom_profile_collect.restype = ctypes.c_int
     lib.rom_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
     lib.rom_profile_collect_calls.restype = ctypes.c_int
@@ -303,6 +305,11 @@ def rom_hybrid_stack_forward(dims, d_ff, blocks, ffns, ffn_pre_norm, eps, x, B, 
 
 def rom_profile_enable(max_calls: int) -> None:
     _check(load_library().rom_profile_enable(max_calls), "rom_profile_enable")
+
+
+def rom_profile_select(stage_mask: int) -> None:
+    """Time only the stages whose bit (1 << index in STAGE_NAMES) is set; the default is all."""
+    _check(load_library().rom_profile_select(stage_mask & 0xFFFFFFFF), "rom_profile_select")
 
 
 def rom_profile_collect():

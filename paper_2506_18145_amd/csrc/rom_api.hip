@@ -114,6 +114,7 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
 constexpr int kProfEvents = ROM_STAGE_COUNT + 1;
 struct Profiler {
   int max_calls = 0, n_calls = 0;
+  unsigned stage_mask = ~0u;         // bit i: stage i is timed
   hipEvent_t *ev = nullptr;          // [max_calls][kProfEvents]
   int *end_of = nullptr;             // [max_calls][ROM_STAGE_COUNT]: event index of the stage's end, -1 = stage did not run
   int *begin_of = nullptr;           // same, for its begin
@@ -128,13 +129,17 @@ struct StageMark {
       on = true;
     }
   }
-  void begin(int, hipStream_t s) {
-    if (!on || last >= 0) return;
+  void begin(int stage, hipStream_t s) {
+    if (!on || last >= 0 || !((g_prof.stage_mask >> stage) & 1u)) return;
     last = call * kProfEvents + next++;
     (void)hipEventRecord(g_prof.ev[last], s);
   }
   void end(int stage, hipStream_t s) {
     if (!on) return;
+    if (!((g_prof.stage_mask >> stage) & 1u)) {     // not timed: the next timed stage records its own begin
+      last = -1;
+      return;
+    }
     const int e = call * kProfEvents + next++;
     (void)hipEventRecord(g_prof.ev[e], s);
     g_prof.begin_of[call * ROM_STAGE_COUNT + stage] = last;
@@ -926,6 +931,11 @@ int rom_profile_enable(int max_calls) {
   for (int i = 0; i < n; ++i)
     if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) return ROM_E_HIP;
   g_prof.max_calls = max_calls;
+  return ROM_OK;
+}
+
+int rom_profile_select(unsigned stage_mask) {
+  g_prof.stage_mask = stage_mask;
   return ROM_OK;
 }
 

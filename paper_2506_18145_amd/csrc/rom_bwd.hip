@@ -55,8 +55,8 @@ constexpr int kGroupsPerTile = kBwdTile / kBwdGroup;
 
 // Scratch of the adjoint scan, all f32.  Units are numbered (sequence * n_chunks + chunk) * n_cb + channel block.
 struct ScanBwdLayout {
-  int n_cb, n_chunks;
-  int64_t chunk_len;          // steps per chunk, a multiple of the tile
+  int n_cb, n_chunks, n_fine;  // channel blocks; chunks of the main kernel and of the carry kernel per sequence
+  int64_t chunk_len, fine_len; // steps per chunk, multiples of the tile; chunk_len is a multiple of fine_len
   int64_t n_units;
   size_t ckpt, carry_p, carry_q, carry_r, part_a, part_d, part_bias, total;   // offsets in floats
 };
@@ -67,16 +67,23 @@ inline ScanBwdLayout scan_bwd_layout(int64_t B, int64_t L, int d_inner) {
   int64_t nc = ceil_div(512, static_cast<int64_t>(l.n_cb) * B);       // two blocks for each of the 256 CUs
   const int64_t max_nc = tiles / 8 > 0 ? tiles / 8 : 1;                 // a chunk is at least 512 steps
   nc = nc < 1 ? 1 : (nc > max_nc ? max_nc : nc);
-  const int64_t tiles_per_chunk = ceil_div(tiles, nc);
+  int64_t tiles_per_chunk = ceil_div(tiles, nc);
+  // the carry kernel is light and latency-bound: it gets chunks of at most 16 tiles, so that many
+  // more of its (small) blocks are resident; the main kernel folds the fine carries
+  const int64_t tiles_per_fine = tiles_per_chunk >= 16 ? 16 : tiles_per_chunk;
+  tiles_per_chunk = ceil_div(tiles_per_chunk, tiles_per_fine) * tiles_per_fine;
   l.n_chunks = static_cast<int>(ceil_div(tiles, tiles_per_chunk));
+  l.n_fine = static_cast<int>(ceil_div(tiles, tiles_per_fine));
   l.chunk_len = tiles_per_chunk * kBwdTile;
+  l.fine_len = tiles_per_fine * kBwdTile;
   l.n_units = B * l.n_chunks * l.n_cb;
+  const size_t n_fine_units = static_cast<size_t>(B) * l.n_fine * l.n_cb;
   size_t off = 0;
   auto take = [&](size_t n) { size_t o = off; off += (n + 63) / 64 * 64; return o; };
   l.ckpt = take(static_cast<size_t>(l.n_units) * tiles_per_chunk * kGroupsPerTile * 256);
-  l.carry_p = take(static_cast<size_t>(l.n_units) * 256);
-  l.carry_q = take(static_cast<size_t>(l.n_units) * 256);
-  l.carry_r = take(static_cast<size_t>(l.n_units) * 256);
+  l.carry_p = take(n_fine_units * 256);
+  l.carry_q = take(n_fine_units * 256);
+  l.carry_r = take(n_fine_units * 256);
   l.part_a = take(static_cast<size_t>(l.n_units) * 256);
   l.part_d = take(static_cast<size_t>(l.n_units) * kBwdCh);
   l.part_bias = take(static_cast<size_t>(l.n_units) * kBwdCh);
@@ -94,60 +101,90 @@ struct BwdSmem {
   float part_b[kBwdHalf][kBwdCh][17], part_c[kBwdHalf][kBwdCh][17];   // [step in half group][channel][state] terms of d_B, d_C
 };
 
+// What the carry kernel needs of a tile: a third of the LDS, so that seven of its blocks fit a CU
+struct BwdCarrySmem {
+  float dt[kBwdTile][kBwdPitch], u[kBwdTile][kBwdPitch], dy[kBwdTile][kBwdPitch];
+  float bc[kBwdTile][33];
+};
+
 // A tile travels from global memory to LDS in two steps, so that the loads of the next tile are in
 // flight while this one is worked on: bwd_fetch_tile (global -> registers), bwd_park_tile (registers -> LDS).
 struct BwdTileRegs {
   float dt[4], u[4], z[4], dg[4], bc[8];
 };
 
+typedef unsigned int bwd_u32x2 __attribute__((ext_vector_type(2)));
+typedef float bwd_f32x4 __attribute__((ext_vector_type(4)));
+// four consecutive elements as floats, one 8-byte (bf16) or 16-byte (f32) load
+__device__ __forceinline__ void bwd_load4(const bf16_t *p, float *f) {
+  const bwd_u32x2 w = *reinterpret_cast<const bwd_u32x2 *>(p);
+  f[0] = __uint_as_float(w.x << 16); f[1] = __uint_as_float(w.x & 0xFFFF0000u);
+  f[2] = __uint_as_float(w.y << 16); f[3] = __uint_as_float(w.y & 0xFFFF0000u);
+}
+__device__ __forceinline__ void bwd_load4(const float *p, float *f) {
+  const bwd_f32x4 w = *reinterpret_cast<const bwd_f32x4 *>(p);
+  f[0] = w.x; f[1] = w.y; f[2] = w.z; f[3] = w.w;
+}
+
+__device__ __forceinline__ void bwd_store4(bf16_t *p, const float *f) {
+  bwd_u32x2 w;
+  w.x = pack_bf16x2(f[0], f[1]);
+  w.y = pack_bf16x2(f[2], f[3]);
+  *reinterpret_cast<bwd_u32x2 *>(p) = w;
+}
+__device__ __forceinline__ void bwd_store4(float *p, const float *f) {
+  bwd_f32x4 w;
+  w.x = f[0]; w.y = f[1]; w.z = f[2]; w.w = f[3];
+  *reinterpret_cast<bwd_f32x4 *>(p) = w;
+}
+
+// thread -> (step row = tid / 4, channels 4 (tid % 4) .. + 3) of every [64][16] tensor and the
+// eight B/C values 8 (tid % 4) .. + 7 of that step
 template <typename T>
 __device__ __forceinline__ void bwd_fetch_tile(BwdTileRegs &r, const T *u_b, const T *dt_b, const T *z_b, int64_t ld_z,
                                                const T *dg_b, const float *bc_b, const float *gate_b, int64_t t0,
                                                int64_t t_end, int d_inner, int tid, bool full) {
-  // thread -> (step row, channel) for the [64][16] tensors, four rounds
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int i = tid + q * 256;
-    const int row = i / kBwdCh, c = i % kBwdCh;
-    const int64_t t = t0 + row;
-    const bool ok = t < t_end;
-    r.dt[q] = ok ? to_f32(dt_b[t * d_inner + c]) : 0.0f;
-    r.u[q] = ok ? to_f32(u_b[t * d_inner + c]) : 0.0f;
+  const int row = tid >> 2, c = (tid & 3) * 4;
+  const int64_t t = t0 + row;
+  if (t < t_end) {
+    bwd_load4(dt_b + t * d_inner + c, r.dt);
+    bwd_load4(u_b + t * d_inner + c, r.u);
     if (full) {
-      r.z[q] = ok ? to_f32(z_b[t * ld_z + c]) : 0.0f;
-      r.dg[q] = ok ? to_f32(dg_b[t * d_inner + c]) * (gate_b ? gate_b[t] : 1.0f) : 0.0f;   // gate weight of Eq. (12)
-    }
-  }
+      bwd_load4(z_b + t * ld_z + c, r.z);
+      bwd_load4(dg_b + t * d_inner + c, r.dg);
+      const float gw = gate_b ? gate_b[t] : 1.0f;                    // gate weight of Eq. (12)
 #pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const int i = tid + q * 256;
-    const int64_t t = t0 + i / 32;
-    r.bc[q] = t < t_end ? bc_b[t * 32 + i % 32] : 0.0f;
+      for (int q = 0; q < 4; ++q) r.dg[q] *= gw;
+    }
+    bwd_load4(bc_b + t * 32 + (tid & 3) * 8, r.bc);
+    bwd_load4(bc_b + t * 32 + (tid & 3) * 8 + 4, r.bc + 4);
+  } else {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r.dt[q] = r.u[q] = r.z[q] = r.dg[q] = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) r.bc[q] = 0.0f;
   }
 }
 
-__device__ __forceinline__ void bwd_park_tile(BwdSmem &sm, const BwdTileRegs &r, int tid, bool full) {
+template <typename Smem, bool kWithDz>
+__device__ __forceinline__ void bwd_park_tile(Smem &sm, const BwdTileRegs &r, int tid, bool full) {
+  const int row = tid >> 2, c = (tid & 3) * 4;
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    const int i = tid + q * 256;
-    const int row = i / kBwdCh, c = i % kBwdCh;
-    sm.dt[row][c] = r.dt[q];
-    sm.u[row][c] = r.u[q];
+    sm.dt[row][c + q] = r.dt[q];
+    sm.u[row][c + q] = r.u[q];
     if (full) {
       const float zs = r.z[q], dgs = r.dg[q];
       const float sig = sigmoid_f32(zs);
-      sm.dy[row][c] = dgs * zs * sig;                                 // g = y * SiLU(z)
-      sm.dzf[row][c] = dgs * sig * (1.0f + zs * (1.0f - sig));
+      sm.dy[row][c + q] = dgs * zs * sig;                             // g = y * SiLU(z)
+      if constexpr (kWithDz) sm.dzf[row][c + q] = dgs * sig * (1.0f + zs * (1.0f - sig));
     }
   }
 #pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const int i = tid + q * 256;
-    sm.bc[i / 32][i % 32] = r.bc[q];
-  }
+  for (int q = 0; q < 8; ++q) sm.bc[row][(tid & 3) * 8 + q] = r.bc[q];
 }
 
-// Carries of one chunk (only launched when the sequences are cut into chunks): grid (n_cb, B * n_chunks).
+// Carries of one fine chunk (only launched when the sequences are cut into chunks): grid (n_cb, B * n_fine).
 //   P = prod_t exp(dt_t a)                       decay over the chunk
 //   Q = state at the chunk's end from a zero state at its start
 //   R = adjoint state leaving the chunk's start from a zero adjoint state at its end
@@ -157,7 +194,7 @@ __global__ __launch_bounds__(256) void scan_bwd_carry_kernel(
     int64_t ld_z, const T *__restrict__ dg, const float *__restrict__ gate, const float *__restrict__ A_log, int64_t L,
     int d_inner, int n_chunks, int64_t chunk_len, float *__restrict__ carry_p, float *__restrict__ carry_q,
     float *__restrict__ carry_r) {
-  __shared__ BwdSmem sm;
+  __shared__ BwdCarrySmem sm;
   const int tid = threadIdx.x;
   const int n = tid & 15, cl = tid >> 4;
   const int c0 = blockIdx.x * kBwdCh, ch = c0 + cl;
@@ -177,7 +214,7 @@ __global__ __launch_bounds__(256) void scan_bwd_carry_kernel(
   bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts, te, d_inner, tid, false);
   for (int64_t ti = 0; ti < n_tiles; ++ti) {
     lds_barrier();
-    bwd_park_tile(sm, regs, tid, false);
+    bwd_park_tile<BwdCarrySmem, false>(sm, regs, tid, false);
     lds_barrier();
     if (ti + 1 < n_tiles)
       bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + (ti + 1) * kBwdTile, te, d_inner, tid, false);
@@ -193,7 +230,7 @@ __global__ __launch_bounds__(256) void scan_bwd_carry_kernel(
   float gq = 0.0f;
   for (int64_t ti = n_tiles - 1; ti >= 0; --ti) {
     lds_barrier();
-    bwd_park_tile(sm, regs, tid, true);
+    bwd_park_tile<BwdCarrySmem, false>(sm, regs, tid, true);
     lds_barrier();
     if (ti > 0)
       bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + (ti - 1) * kBwdTile, te, d_inner, tid, true);
@@ -213,8 +250,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void scan_bwd_kernel(
     const T *__restrict__ u, const T *__restrict__ dt, const float *__restrict__ bc, const T *__restrict__ z,
     int64_t ld_z, const T *__restrict__ dg, const float *__restrict__ gate, const float *__restrict__ A_log,
-    const float *__restrict__ D, int64_t n_seq, int64_t L, int d_inner, int n_chunks, int64_t chunk_len,
-    float *__restrict__ ckpt, const float *__restrict__ carry_p, const float *__restrict__ carry_q,
+    const float *__restrict__ D, int64_t n_seq, int64_t L, int d_inner, int n_chunks, int64_t chunk_len, int n_fine,
+    int fine_per_chunk, float *__restrict__ ckpt, const float *__restrict__ carry_p, const float *__restrict__ carry_q,
     const float *__restrict__ carry_r, T *__restrict__ d_pre, T *__restrict__ d_u, T *__restrict__ d_z, int64_t ld_dz,
     float *__restrict__ d_bc_part, float *__restrict__ part_a, float *__restrict__ part_d,
     float *__restrict__ part_bias) {
@@ -240,15 +277,16 @@ __global__ __launch_bounds__(256) void scan_bwd_kernel(
   const float *bc_b = bc + b * L * 32;
   const float *gate_b = gate ? gate + b * L : nullptr;
 
-  // ---- prologue: the carries of the chunks before (state) and after (adjoint state) this one
+  // ---- prologue: the carries of the fine chunks before (state) and after (adjoint state) this chunk
   float h = 0.0f, dh = 0.0f;
   if (n_chunks > 1) {
-    const int64_t unit0 = b * n_chunks * gridDim.x + blockIdx.x;      // chunk 0 of this sequence and channel block
-    for (int64_t j = 0; j < k; ++j) {
+    const int64_t unit0 = b * n_fine * gridDim.x + blockIdx.x;        // fine chunk 0 of this sequence and channel block
+    const int64_t f0 = k * fine_per_chunk;
+    for (int64_t j = 0; j < f0; ++j) {
       const int64_t at = (unit0 + j * gridDim.x) * 256 + tid;
       h = fmaf(carry_p[at], h, carry_q[at]);
     }
-    for (int64_t j = n_chunks - 1; j > k; --j) {
+    for (int64_t j = n_fine - 1; j >= f0 + fine_per_chunk; --j) {
       const int64_t at = (unit0 + j * gridDim.x) * 256 + tid;
       dh = fmaf(carry_p[at], dh, carry_r[at]);
     }
@@ -259,7 +297,7 @@ __global__ __launch_bounds__(256) void scan_bwd_kernel(
   bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts, te, d_inner, tid, false);
   for (int64_t ti = 0; ti < n_tiles; ++ti) {
     lds_barrier();
-    bwd_park_tile(sm, regs, tid, false);
+    bwd_park_tile<BwdSmem, true>(sm, regs, tid, false);
     lds_barrier();
     if (ti + 1 < n_tiles)      // the next tile; after the last one, the same tile again with the factors pass 2 needs
       bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + (ti + 1) * kBwdTile, te, d_inner, tid, false);
@@ -283,7 +321,7 @@ __global__ __launch_bounds__(256) void scan_bwd_kernel(
     // the checkpoint of a group is fetched one group ahead of its use
     float ck_next = ck[(ti * kGroupsPerTile + kGroupsPerTile - 1) * 256 + tid];
     lds_barrier();
-    bwd_park_tile(sm, regs, tid, true);
+    bwd_park_tile<BwdSmem, true>(sm, regs, tid, true);
     lds_barrier();
     if (ti > 0)
       bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, t0 - kBwdTile, te, d_inner, tid, true);
@@ -340,23 +378,29 @@ __global__ __launch_bounds__(256) void scan_bwd_kernel(
         lds_barrier();
       }
     }
-    // the tile's per-channel outputs
-#pragma unroll
-    for (int i = tid; i < kBwdTile * kBwdCh; i += 256) {
-      const int row = i / kBwdCh, c = i % kBwdCh;
+    // the tile's outputs, in the fetch's thread map
+    {
+      const int row = tid >> 2, c = (tid & 3) * 4;
       const int64_t t = t0 + row;
       if (t < te) {
         const int64_t at = (b * L + t) * d_inner + c0 + c;
-        d_pre[at] = from_f32<T>(sm.o_pre[row][c]);
-        d_u[at] = from_f32<T>(sm.o_u[row][c]);
-        d_z[(b * L + t) * ld_dz + c0 + c] = from_f32<T>(sm.o_z[row][c]);
-      }
-    }
+        float v[4];
 #pragma unroll
-    for (int i = tid; i < kBwdTile * 32; i += 256) {
-      const int row = i / 32, c = i % 32;
-      const int64_t t = t0 + row;
-      if (t < te) d_bc_part[(static_cast<int64_t>(blockIdx.x) * n_tok + b * L + t) * 32 + c] = sm.o_bc[row][c];
+        for (int q = 0; q < 4; ++q) v[q] = sm.o_pre[row][c + q];
+        bwd_store4(d_pre + at, v);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = sm.o_u[row][c + q];
+        bwd_store4(d_u + at, v);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = sm.o_z[row][c + q];
+        bwd_store4(d_z + (b * L + t) * ld_dz + c0 + c, v);
+        float *dst = d_bc_part + (static_cast<int64_t>(blockIdx.x) * n_tok + b * L + t) * 32 + (tid & 3) * 8;
+        float w[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) w[q] = sm.o_bc[row][(tid & 3) * 8 + q];
+        bwd_store4(dst, w);
+        bwd_store4(dst + 4, w + 4);
+      }
     }
   }
   part_a[unit * 256 + tid] = acc_a * a_nat;                            // d A_log = d A * A
@@ -796,15 +840,16 @@ static hipError_t launch_scan_backward_t(const void *u, const void *dt, const fl
   const ScanBwdLayout l = scan_bwd_layout(B, L, d_inner);
   const dim3 grid(static_cast<unsigned>(l.n_cb), static_cast<unsigned>(B * l.n_chunks));
   if (l.n_chunks > 1) {
-    hipLaunchKernelGGL((scan_bwd_carry_kernel<T>), grid, dim3(256), 0, s, static_cast<const T *>(u),
+    const dim3 fine_grid(static_cast<unsigned>(l.n_cb), static_cast<unsigned>(B * l.n_fine));
+    hipLaunchKernelGGL((scan_bwd_carry_kernel<T>), fine_grid, dim3(256), 0, s, static_cast<const T *>(u),
                        static_cast<const T *>(dt), bc, static_cast<const T *>(z), ld_z, static_cast<const T *>(dg), gate,
-                       A_log, L, d_inner, l.n_chunks, l.chunk_len, ws + l.carry_p, ws + l.carry_q, ws + l.carry_r);
+                       A_log, L, d_inner, l.n_fine, l.fine_len, ws + l.carry_p, ws + l.carry_q, ws + l.carry_r);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL((scan_bwd_kernel<T>), grid, dim3(256), 0, s, static_cast<const T *>(u), static_cast<const T *>(dt),
                      bc, static_cast<const T *>(z), ld_z, static_cast<const T *>(dg), gate, A_log, D, B, L, d_inner,
-                     l.n_chunks, l.chunk_len, ws + l.ckpt, ws + l.carry_p, ws + l.carry_q, ws + l.carry_r,
+                     l.n_chunks, l.chunk_len, l.n_fine, static_cast<int>(l.chunk_len / l.fine_len), ws + l.ckpt, ws + l.carry_p, ws + l.carry_q, ws + l.carry_r,
                      static_cast<T *>(d_pre), static_cast<T *>(d_u), static_cast<T *>(d_z), ld_dz, d_bc_part,
                      ws + l.part_a, ws + l.part_d, ws + l.part_bias);
   hipError_t e = hipGetLastError();
@@ -819,7 +864,7 @@ hipError_t launch_scan_backward(int dtype, const void *u, const void *dt, const 
                                 int64_t L, int d_inner, float *ckpt, float *d_bc_part, void *d_pre, void *d_u, void *d_z,
                                 int64_t ld_dz, float *d_bc, float *d_A_log, float *d_D, float *d_dt_bias,
                                 hipStream_t s) {
-  if (B * scan_bwd_layout(B, L, d_inner).n_chunks > 65535) return hipErrorInvalidValue;
+  if (B * scan_bwd_layout(B, L, d_inner).n_fine > 65535) return hipErrorInvalidValue;
   hipError_t e = dtype == ROM_DTYPE_BF16
                      ? launch_scan_backward_t<bf16_t>(u, dt, bc, z, ld_z, dg, gate, A_log, D, B, L, d_inner, ckpt, d_bc_part,
                                                       d_pre, d_u, d_z, ld_dz, d_A_log, d_D, d_dt_bias, s)
