@@ -1,0 +1,161 @@
+// Host-side exercise of the C ABI for a build with -fsanitize=address,undefined (host code only;
+// tests/test_abi_sanitized.py compiles the library's sources host-only together with this file and
+// runs the result).  Every call here returns before anything is launched on a GPU: workspace
+// planning, argument validation, error strings, the profiling bookkeeping with no recorded calls.
+// What the sanitizers watch: the planners' size arithmetic at the edges of the supported range,
+// reads of the dims / weights / layout structs, and the host-side bookkeeping arrays.
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <initializer_list>
+#include <vector>
+
+#include "rom.h"
+
+// The library's objects are compiled host-only here, so there is no device image to register: the
+// registration hooks that the compiler's start-up code calls are satisfied by these no-ops (the
+// test links them into the executable, ahead of the HIP runtime's), and the image symbols the
+// objects refer to are defined as absolute zeros on the link line.  No kernel can be launched in
+// this build, and nothing below tries to.
+extern "C" {
+void **__hipRegisterFatBinary(const void *) {
+  static void *handle = nullptr;
+  return &handle;
+}
+void __hipUnregisterFatBinary(void **) {}
+void __hipRegisterFunction(void **, const void *, char *, const char *, unsigned, void *, void *, void *, void *, int *) {}
+void __hipRegisterVar(void **, void *, char *, const char *, int, size_t, int, int) {}
+void __hipRegisterManagedVar(void *, void **, void *, const char *, size_t, unsigned) {}
+}
+
+static int failures = 0;
+#define CHECK(cond)                                                          \
+  do {                                                                       \
+    if (!(cond)) {                                                           \
+      std::fprintf(stderr, "%s:%d: check failed: %s\n", __FILE__, __LINE__, #cond); \
+      ++failures;                                                            \
+    }                                                                        \
+  } while (0)
+
+static rom_dims dims_of(int d_model, int d_inner, int dt_rank, int E, int K, int Ex, int dtype, int gate_mode) {
+  rom_dims d;
+  d.d_model = d_model; d.d_inner = d_inner; d.d_state = 16; d.d_conv = 4; d.dt_rank = dt_rank;
+  d.n_experts = E; d.top_k = K; d.n_experts_xdt = Ex; d.dtype = dtype; d.gate_mode = gate_mode;
+  return d;
+}
+
+int main() {
+  // an aligned host block standing in for "some non-NULL, 256-byte aligned pointer": never dereferenced
+  // by the calls below (they fail validation, or have nothing to do, before any launch)
+  std::vector<unsigned char> block(8192 + 256);
+  unsigned char *addr = reinterpret_cast<unsigned char *>((reinterpret_cast<uintptr_t>(block.data()) + 255) / 256 * 256);
+  rom_weights w_null;
+  std::memset(&w_null, 0, sizeof(w_null));
+  rom_weights w;
+  w.w_router = addr; w.b_router = nullptr; w.w_in = addr; w.conv_w = reinterpret_cast<const float *>(addr);
+  w.conv_b = nullptr; w.w_x = addr; w.w_dt = addr; w.dt_bias = reinterpret_cast<const float *>(addr);
+  w.A_log = reinterpret_cast<const float *>(addr); w.D = reinterpret_cast<const float *>(addr); w.w_out = addr;
+
+  // ---- planners over the paper's shapes and the edges of the supported range
+  const rom_dims shapes[] = {
+      dims_of(64, 128, 4, 4, 1, 4, ROM_DTYPE_F32, 0),        dims_of(1024, 2048, 64, 8, 1, 8, ROM_DTYPE_BF16, 0),
+      dims_of(2048, 4096, 128, 8, 1, 8, ROM_DTYPE_BF16, 0),  dims_of(2048, 4096, 128, 16, 2, 16, ROM_DTYPE_BF16, 1),
+      dims_of(2048, 4096, 128, 8, 1, 1, ROM_DTYPE_BF16, 0),  dims_of(8, 16, 1, 1, 1, 1, ROM_DTYPE_F32, 0),
+      dims_of(4096, 8192, 256, 64, 8, 64, ROM_DTYPE_BF16, 1),
+  };
+  const int64_t batches[] = {1, 2, 7, 256, 65535};
+  const int64_t lengths[] = {1, 3, 64, 4097, 16384, int64_t(1) << 20};
+  for (const rom_dims &d : shapes) {
+    for (int64_t B : batches)
+      for (int64_t L : lengths) {
+        if (B * L * d.top_k > (int64_t(1) << 30)) continue;
+        const size_t bytes = rom_workspace_bytes(&d, B, L);
+        CHECK(bytes > 0);
+        rom_ws_layout lay;
+        CHECK(rom_workspace_layout(&d, B, L, &lay) == ROM_OK);
+        CHECK(lay.total_bytes == bytes);
+        CHECK(lay.expert_idx < bytes && lay.logits < bytes && lay.xz < bytes && lay.g < bytes);
+        CHECK(lay.xz % 256 == 0 && lay.g % 256 == 0);
+        const size_t route = rom_route_workspace_bytes(&d, B * L);
+        CHECK(route > 0 && route <= rom_workspace_bytes(&d, B * L, 1));
+        if (B * L <= (int64_t(1) << 24)) {
+          const size_t bwd = rom_backward_workspace_bytes(&d, B, L);
+          if (d.top_k == 1) CHECK(bwd > bytes);
+        }
+        const size_t ffn = rom_ffn_workspace_bytes(&d, 2 * d.d_model, B * L);
+        CHECK(ffn > 0);
+      }
+  }
+  // invalid or unsupported shapes: size 0 / an error code, never a plan
+  {
+    rom_dims d = shapes[0];
+    rom_ws_layout lay;
+    d.d_state = 8;   CHECK(rom_workspace_bytes(&d, 1, 8) == 0);  d = shapes[0];
+    d.top_k = 5;     CHECK(rom_workspace_bytes(&d, 1, 8) == 0);  d = shapes[0];
+    d.dtype = 7;     CHECK(rom_workspace_bytes(&d, 1, 8) == 0);  d = shapes[0];
+    d.d_conv = 3;    CHECK(rom_workspace_layout(&d, 1, 8, &lay) == ROM_E_UNSUPPORTED);  d = shapes[0];
+    d.top_k = 0;     CHECK(rom_workspace_layout(&d, 1, 8, &lay) == ROM_E_INVAL);  d = shapes[0];
+    d.n_experts_xdt = 2;  CHECK(rom_workspace_layout(&d, 1, 8, &lay) == ROM_E_INVAL);  d = shapes[0];
+    CHECK(rom_workspace_bytes(nullptr, 1, 8) == 0);
+    CHECK(rom_workspace_layout(&d, 1, 8, nullptr) == ROM_E_INVAL);
+    CHECK(rom_workspace_bytes(&d, -1, 8) == 0);
+    CHECK(rom_backward_workspace_bytes(nullptr, 1, 8) == 0);
+  }
+
+  // ---- argument validation of the launching entry points: refused before any launch
+  {
+    const rom_dims d = shapes[0];
+    CHECK(rom_layer_forward(&d, &w_null, nullptr, 1, 8, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr) == ROM_E_INVAL);
+    CHECK(rom_layer_forward(nullptr, &w, addr, 1, 8, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_route(&d, &w_null, nullptr, 8, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr) == ROM_E_INVAL);
+    CHECK(rom_step(&d, &w_null, nullptr, 4, nullptr, nullptr, nullptr, nullptr, 0, nullptr) == ROM_E_INVAL);
+    CHECK(rom_step_static(&d, &w_null, nullptr, 4, nullptr, nullptr, nullptr, nullptr) == ROM_E_INVAL);
+    rom_grads g;
+    std::memset(&g, 0, sizeof(g));
+    CHECK(rom_layer_backward(&d, &w, addr, 1, 8, addr, addr + 4096, &g, addr, 4096, nullptr) == ROM_E_INVAL);   // NULL gradient pointers
+    CHECK(rom_layer_backward(&d, &w, addr, 1, 8, addr, addr + 4096, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+    // workspace too small
+    CHECK(rom_layer_forward(&d, &w, addr, 1, 8, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 16, nullptr) == ROM_E_WORKSPACE);
+    // sizes beyond the supported range
+    const rom_dims d2 = shapes[3];
+    CHECK(rom_layer_forward(&d2, &w, addr, 65536, 1, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_UNSUPPORTED);
+    CHECK(rom_layer_forward(&d2, &w, addr, 1, (int64_t(1) << 29) + 1, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_UNSUPPORTED);
+    CHECK(rom_layer_forward(&d2, &w, addr, 65535, 1, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+    // empty input: a successful no-op
+    CHECK(rom_layer_forward(&d, &w, addr, 0, 8, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_OK);
+    CHECK(rom_layer_forward(&d, &w, addr, 2, 0, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_OK);
+    CHECK(rom_step(&d, &w, addr, 0, nullptr, nullptr, addr + 4096, addr, 4096, nullptr) == ROM_OK);
+    int32_t *ip = reinterpret_cast<int32_t *>(addr);
+    float *fp = reinterpret_cast<float *>(addr);
+    CHECK(rom_route(&d, &w, addr, 0, ip, fp, ip, ip, ip, ip, nullptr, addr, 4096, nullptr) == ROM_OK);
+    // balance statistics: the mean over no tokens is undefined
+    CHECK(rom_balance_stats(&d, fp, ip, 0, 1e-3f, fp, fp, fp, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_balance_stats(&d, nullptr, ip, 8, 1e-3f, fp, fp, fp, addr, 4096, nullptr) == ROM_E_INVAL);
+    // the backward of top-2 routing is not built
+    CHECK(rom_backward_workspace_bytes(&d2, 1, 64) == 0);
+  }
+
+  // ---- strings and the profiling bookkeeping
+  CHECK(std::strcmp(rom_strerror(ROM_OK), "ok") == 0);
+  for (int code : {ROM_E_INVAL, ROM_E_WORKSPACE, ROM_E_UNSUPPORTED, ROM_E_HIP, ROM_E_STATIC_LIMIT, -99})
+    CHECK(std::strlen(rom_strerror(code)) > 5);
+  for (int s = -1; s <= ROM_STAGE_COUNT; ++s) CHECK(rom_stage_name(s) != nullptr);
+  CHECK(rom_profile_enable(0) == ROM_OK);
+  CHECK(rom_profile_select(1u << ROM_STAGE_IN_PROJ) == ROM_OK);
+  {
+    double ms[ROM_STAGE_COUNT * 4];
+    int n = -1;
+    CHECK(rom_profile_collect(ms, &n) == ROM_OK && n == 0);
+    CHECK(rom_profile_collect_calls(ms, 4, &n) == ROM_OK && n == 0);
+    CHECK(rom_profile_collect(nullptr, &n) == ROM_E_INVAL);
+  }
+  CHECK(rom_profile_select(~0u) == ROM_OK);
+
+  if (failures) {
+    std::fprintf(stderr, "%d check(s) failed\n", failures);
+    return 1;
+  }
+  std::printf("all checks passed\n");
+  return 0;
+}
