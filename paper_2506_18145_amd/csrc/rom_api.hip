@@ -28,7 +28,30 @@ struct Plan {                 // byte offsets inside the workspace
   size_t scan_q, scan_p;      // chunk end states / decays of a time-chunked scan
   size_t rstd;                // f32 [N]: 1 / rms of every token of a pre-norm block's input
   int xproj_slices;           // inner-dimension slices the xdbl buffer has room for
+  // K == 2 on long inputs: the routed dt projection runs as two passes over the tokens, pass r on
+  // every token's r-th expert, the second accumulating into the token-order output and activating
+  // (no per-slot staging buffer, no slot sum)
+  bool rank_passes;
+  size_t rank_offsets, rank_tok, rank_blocks;   // i32 [K][E + 1], i32 [K][N], scratch of the per-rank grouping
 };
+
+// Rank passes need the accumulate-then-activate form of the dt projection, which only the
+// streaming small-K kernel has (bf16, dt_rank 32 / 64 / 128); short inputs keep the per-slot path
+// (its single launches suit the decode step better than two short ones).  Only K == 2: the output
+// between two passes is stored in the activation type, so with two passes exactly one addend is
+// rounded before the sum - one rounding fewer than per-slot outputs - while every further pass
+// would round the growing running sum again (measured at K = 4: 1.7 times the per-slot path's
+// error, over the tolerance on dt).
+// Only the dt projection: the in projection was run the same way and measured slower than the
+// per-slot path (d_model 2048, 16 experts, 16K tokens: 1.29 ms against 1.19): its second pass reads
+// the first one's 256 MiB back in the epilogue, through the L1 miss queue and with nothing to
+// overlap, which costs more than the slot sum's streaming read; the x projection gained nothing
+// (its passes are two more short launches).  The dt projection's accumulating read happens in a
+// kernel that is store-bound anyway: 0.30 -> 0.18 ms.
+bool use_rank_passes(const rom_dims *d, int64_t n_tok) {
+  if (d->top_k != 2 || n_tok < 2048 || d->dtype != ROM_DTYPE_BF16 || d->n_experts_xdt <= 1) return false;
+  return d->dt_rank == 32 || d->dt_rank == 64 || d->dt_rank == 128;
+}
 
 int check_dims(const rom_dims *d) {
   if (!d) return ROM_E_INVAL;
@@ -77,6 +100,7 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   const size_t De = d->d_inner, Dm = d->d_model, R = d->dt_rank;
   const bool multi = K > 1;
   const bool routed_xdt = d->n_experts_xdt > 1;
+  p.rank_passes = use_rank_passes(d, n_tok);
   p.xproj_slices = xproj_slices_for(d, n_tok * (routed_xdt ? d->top_k : 1));
   p.expert_idx = take(S * 4);
   p.gate = take(S * 4);
@@ -95,7 +119,7 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   p.dt_low = take(N * R * b);
   p.bc = take(N * 32 * 4);
   p.dt = take(N * De * b);
-  p.dt_raw = (multi && routed_xdt) ? take(S * De * b) : kNone;   // per-slot dt pre-activations, in T like every expert output
+  p.dt_raw = (multi && routed_xdt && !p.rank_passes) ? take(S * De * b) : kNone;   // per-slot dt pre-activations, in T like every expert output
   p.g = take(N * De * b);
   p.op_sorted = multi ? take(S * Dm * b) : kNone;
   // the conv writes its end state beside the old one only when a sequence is cut into runs
@@ -104,6 +128,9 @@ Plan make_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   p.scan_q = take(chunk_bytes);
   p.scan_p = take(chunk_bytes);
   p.rstd = take(N * 4);
+  p.rank_offsets = p.rank_passes ? take(K * (E + 1) * 4) : kNone;
+  p.rank_tok = p.rank_passes ? take(S * 4) : kNone;
+  p.rank_blocks = p.rank_passes ? take(rank_grouping_block_counts_bytes(n_tok, d->n_experts, d->top_k)) : kNone;
   p.total = off;
   return p;
 }
@@ -193,7 +220,8 @@ struct BlockOpts {
 int route_into(const rom_dims *d, const rom_weights *w, const void *x, int64_t n_tok,
                int32_t *expert_idx, float *gate, int32_t *counts, int32_t *offsets, int32_t *perm,
                int32_t *inv_perm, int32_t *tok_of_pos, int32_t *block_counts, float *logits,
-               const BlockOpts *blk, float *rstd, hipStream_t s, StageMark *mark) {
+               const BlockOpts *blk, float *rstd, hipStream_t s, StageMark *mark, int32_t *rank_offsets = nullptr,
+               int32_t *rank_tok = nullptr, int32_t *rank_blocks = nullptr) {
   if (mark) mark->begin(ROM_STAGE_ROUTE, s);
   ROM_TRY(launch_route_topk(d->dtype, x, w->w_router, w->b_router, n_tok, d->d_model, d->n_experts,
                             d->top_k, d->gate_mode, expert_idx, gate, logits, blk ? blk->norm_w : nullptr,
@@ -202,6 +230,8 @@ int route_into(const rom_dims *d, const rom_weights *w, const void *x, int64_t n
   if (mark) mark->begin(ROM_STAGE_PERMUTE, s);
   ROM_TRY(launch_permutation(expert_idx, n_tok * d->top_k, d->n_experts, d->top_k, block_counts,
                              counts, offsets, perm, inv_perm, tok_of_pos, s));
+  if (rank_offsets)
+    ROM_TRY(launch_rank_grouping(expert_idx, n_tok, d->n_experts, d->top_k, rank_blocks, rank_offsets, rank_tok, s));
   if (mark) mark->end(ROM_STAGE_PERMUTE, s);
   return ROM_OK;
 }
@@ -239,7 +269,10 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   rc = route_into(d, w, x, N, reinterpret_cast<int32_t *>(at(p.expert_idx)), gate,
                   reinterpret_cast<int32_t *>(at(p.counts)), offsets, reinterpret_cast<int32_t *>(at(p.perm)),
                   inv_perm, tok_of_pos, reinterpret_cast<int32_t *>(at(p.block_counts)),
-                  reinterpret_cast<float *>(at(p.logits)), blk, reinterpret_cast<float *>(at(p.rstd)), s, &mark);
+                  reinterpret_cast<float *>(at(p.logits)), blk, reinterpret_cast<float *>(at(p.rstd)), s, &mark,
+                  p.rank_passes ? reinterpret_cast<int32_t *>(at(p.rank_offsets)) : nullptr,
+                  p.rank_passes ? reinterpret_cast<int32_t *>(at(p.rank_tok)) : nullptr,
+                  p.rank_passes ? reinterpret_cast<int32_t *>(at(p.rank_blocks)) : nullptr);
   if (rc != ROM_OK) return rc;
 
   // the routed GEMMs: expert e's rows are the sorted positions [offsets[e], offsets[e + 1])
@@ -247,6 +280,16 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
     ga.n_groups = E;
     ga.M = S;
     ga.offsets = offsets;
+  };
+  // pass r of a projection run rank by rank: the N tokens grouped by their r-th expert; rows are
+  // gathered from and scattered to token order through the same map
+  const bool passes = p.rank_passes;
+  auto rank_pass = [&](GemmArgs &ga, int r) {
+    ga.n_groups = E;
+    ga.M = N;
+    ga.offsets = reinterpret_cast<const int32_t *>(at(p.rank_offsets)) + static_cast<size_t>(r) * (E + 1);
+    ga.a_rows = reinterpret_cast<const int32_t *>(at(p.rank_tok)) + static_cast<size_t>(r) * N;
+    ga.c_rows = ga.a_rows;
   };
 
   // in / gate projection, Eq. (10)/(11): gather token rows, scatter back to token order (K == 1)
@@ -319,7 +362,17 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   ga.dtype = d->dtype;
   ga.A = at(p.dt_low); ga.lda = R; ga.a_span = N * R;
   ga.W = w->w_dt; ga.N = De; ga.K = R; ga.ldc = De;
-  if (routed_xdt && multi) {
+  if (passes) {
+    // dt[n] = softplus(sum_r W_dt[e_r(n)] dt_low[n] + bias): the sums accumulate in dt (without the
+    // bias, so that what is stored in T between the passes is small), the last pass activates
+    ga.C = at(p.dt);
+    for (int r = 0; r < K; ++r) {
+      rank_pass(ga, r);
+      ga.residual = r > 0 ? at(p.dt) : nullptr;
+      if (r == K - 1) { ga.bias = w->dt_bias; ga.softplus = 1; }
+      ROM_TRY(launch_grouped_gemm(ga, s));
+    }
+  } else if (routed_xdt && multi) {
     ga.a_rows = tok_of_pos;
     routed(ga);
     ga.C = at(p.dt_raw);     // one expert's output per slot, stored in T as in_proj's; summed in fp32 below

@@ -23,6 +23,7 @@ namespace rom {
 namespace {
 
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
@@ -264,7 +265,8 @@ __device__ __forceinline__ void mfma_epilogue(const GemmArgs &a, const TileCoord
       float scale = 1.0f;
       if (EPI == kEpiRowScale || EPI == kEpiRowScaleResidual) {
         const int64_t p = tc.row0 + wm * WTM + i * 32 + frag_row;
-        scale = p < tc.row_end ? a.row_scale[a.c_rows ? a.c_rows[p] : p] : 0.0f;
+        // (the residual epilogue without a row scale: accumulation into the output, scale 1)
+        scale = p < tc.row_end ? (a.row_scale ? a.row_scale[a.c_rows ? a.c_rows[p] : p] : 1.0f) : 0.0f;
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
@@ -748,8 +750,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_tails_kernel(const GemmArgs
 // workgroups (16 waves) share a CU.
 constexpr int kSkBM = 512, kSkBN = 128, kSkWaves = 8;
 
-// PLAIN: no bias, no softplus (the per-slot outputs of K > 1, which the slot sum adds up and activates).
-template <int KSTEPS, bool PLAIN>
+// PLAIN: no bias, no softplus.  RES: the rows of a.residual (the output's layout and row map) are
+// added to the sums before bias and activation: the passes of K > 1 accumulate into the output,
+// the last one activates.
+template <int KSTEPS, bool PLAIN, bool RES = false>
 __global__ __launch_bounds__(kSkWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 8)))
 void gemm_bf16_smallk_kernel(const GemmArgs a) {
   constexpr int KC = KSTEPS * 2;                       // 16-byte chunks per row of A / W
@@ -819,13 +823,23 @@ void gemm_bf16_smallk_kernel(const GemmArgs a) {
         for (int q = 0; q < 4; ++q) {
           const int lcol = j * 32 + q * 8 + frag_half * 4;
           const float4 b4 = *reinterpret_cast<const float4 *>(bias_s + h * kHalf + lcol);
+          float v0 = acc[j][4 * q], v1 = acc[j][4 * q + 1], v2 = acc[j][4 * q + 2], v3 = acc[j][4 * q + 3];
+          if constexpr (RES) {
+            const int gcol = tc.n0 + h * kHalf + lcol;
+            if (gcol < a.N) {
+              const u32x2_t o = *reinterpret_cast<const u32x2_t *>(static_cast<const bf16_t *>(a.residual) +
+                                                                   static_cast<int64_t>(crow) * a.ldc + gcol);
+              v0 += __uint_as_float(o.x << 16); v1 += __uint_as_float(o.x & 0xFFFF0000u);
+              v2 += __uint_as_float(o.y << 16); v3 += __uint_as_float(o.y & 0xFFFF0000u);
+            }
+          }
           uint2 pk;
           if constexpr (PLAIN) {
-            pk.x = pack_bf16x2(acc[j][4 * q], acc[j][4 * q + 1]);
-            pk.y = pack_bf16x2(acc[j][4 * q + 2], acc[j][4 * q + 3]);
+            pk.x = pack_bf16x2(v0, v1);
+            pk.y = pack_bf16x2(v2, v3);
           } else {
-            pk.x = pack_bf16x2(softplus_fast(acc[j][4 * q] + b4.x), softplus_fast(acc[j][4 * q + 1] + b4.y));
-            pk.y = pack_bf16x2(softplus_fast(acc[j][4 * q + 2] + b4.z), softplus_fast(acc[j][4 * q + 3] + b4.w));
+            pk.x = pack_bf16x2(softplus_fast(v0 + b4.x), softplus_fast(v1 + b4.y));
+            pk.y = pack_bf16x2(softplus_fast(v2 + b4.z), softplus_fast(v3 + b4.w));
           }
           *reinterpret_cast<uint2 *>(stage + frag_row * kPitch + lcol * 2) = pk;
         }
@@ -948,14 +962,23 @@ hipError_t launch_mfma(const GemmArgs &a, hipStream_t s) {
   return launch_mfma_k<BM, BN, WM, WN, EPI, true>(a, s);
 }
 
-template <int KSTEPS, bool PLAIN>
-hipError_t launch_smallk(const GemmArgs &a, hipStream_t s) {
+template <int KSTEPS, bool PLAIN, bool RES>
+hipError_t launch_smallk_t(const GemmArgs &a, hipStream_t s) {
   constexpr int kSmem = kSkBN * KSTEPS * 2 * 16 + kSkBN * 4 + kSkWaves * 32 * (kSkBN + 16);
   static LdsAttrOnce attr;
-  const hipError_t e = attr.ensure(reinterpret_cast<const void *>(&gemm_bf16_smallk_kernel<KSTEPS, PLAIN>), kSmem);
+  const hipError_t e = attr.ensure(reinterpret_cast<const void *>(&gemm_bf16_smallk_kernel<KSTEPS, PLAIN, RES>), kSmem);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((gemm_bf16_smallk_kernel<KSTEPS, PLAIN>), dim3(grid_tiles(a, kSkBM, kSkBN)), dim3(kSkWaves * 64), kSmem, s, a);
+  hipLaunchKernelGGL((gemm_bf16_smallk_kernel<KSTEPS, PLAIN, RES>), dim3(grid_tiles(a, kSkBM, kSkBN)), dim3(kSkWaves * 64), kSmem, s, a);
   return hipGetLastError();
+}
+template <int KSTEPS, bool PLAIN>
+hipError_t launch_smallk(const GemmArgs &a, hipStream_t s) {
+  return a.residual ? launch_smallk_t<KSTEPS, PLAIN, true>(a, s) : launch_smallk_t<KSTEPS, PLAIN, false>(a, s);
+}
+// whether the streaming small-K kernel takes the call (inner dimension 32, 64 or 128, dense rows of A)
+bool smallk_takes(const GemmArgs &a) {
+  return kUseSmallK && a.lda >= a.K && a.M < (1ll << 31) && (a.K == 128 || a.K == 64 || a.K == 32) &&
+         !a.row_scale && !a.c_is_f32;
 }
 
 template <int BN, int WM, int WN, int EPI>
@@ -1022,7 +1045,7 @@ bool grouped_gemm_on_mfma(const GemmArgs &a) {
          static_cast<int64_t>(a.N) * a.K < (1ll << 32) &&
          !(a.bias && !a.softplus) && !(a.softplus && !a.bias) &&
          !(a.row_scale && (a.bias || a.c_is_f32)) && !(a.bias && a.c_is_f32) &&
-         !(a.residual && !a.row_scale) && (reinterpret_cast<uintptr_t>(a.residual) % 16 == 0) &&
+         !(a.residual && a.c_is_f32) && (reinterpret_cast<uintptr_t>(a.residual) % 16 == 0) &&
          !(a.swiglu && (a.bias || a.c_is_f32 || a.residual || a.N % 16 != 0));
 }
 
@@ -1068,21 +1091,22 @@ hipError_t launch_grouped_gemm(const GemmArgs &args, hipStream_t s) {
     return launch_mfma_tiles<kEpiPlainF32>(a, s);
   }
   if (a.bias) {
-    if (kUseSmallK && a.lda >= a.K && a.M < (1ll << 31)) {
+    if (smallk_takes(a)) {
       if (a.K == 128) return launch_smallk<8, false>(a, s);
       if (a.K == 64) return launch_smallk<4, false>(a, s);
-      if (a.K == 32) return launch_smallk<2, false>(a, s);
+      return launch_smallk<2, false>(a, s);
     }
+    if (a.residual) return hipErrorInvalidValue;       // bias + activation on top of an accumulated output: small-K kernel only
     return launch_mfma_tiles<kEpiBiasSoftplus>(a, s);
   }
-  if (a.row_scale && a.residual) return launch_mfma_tiles<kEpiRowScaleResidual>(a, s);
-  if (a.row_scale) return launch_mfma_tiles<kEpiRowScale>(a, s);
   // short inner dimension, many rows, wide output: the streaming kernel without its activation
-  if (kUseSmallK && a.lda >= a.K && a.M < (1ll << 31) && a.M >= 4096 && a.N >= 1024) {
+  if (smallk_takes(a) && a.M >= 4096 && a.N >= 1024) {
     if (a.K == 128) return launch_smallk<8, true>(a, s);
     if (a.K == 64) return launch_smallk<4, true>(a, s);
-    if (a.K == 32) return launch_smallk<2, true>(a, s);
+    return launch_smallk<2, true>(a, s);
   }
+  if (a.residual) return launch_mfma_tiles<kEpiRowScaleResidual>(a, s);
+  if (a.row_scale) return launch_mfma_tiles<kEpiRowScale>(a, s);
   return launch_mfma_tiles<kEpiPlain>(a, s);
 }
 

@@ -50,6 +50,14 @@ hipError_t launch_permutation(const int32_t *expert_idx, int64_t n_slots, int n_
                               int32_t *block_counts, int32_t *counts, int32_t *offsets,
                               int32_t *perm, int32_t *inv_perm, int32_t *tok_of_pos, hipStream_t s);
 
+// K > 1: for every rank r < K, the N tokens grouped by their r-th expert (stable): rank_offsets
+// i32 [K][E + 1] (each rank's offsets start at 0), tok_of_rank_pos i32 [K][N] = token at that
+// rank's sorted position; block_counts: scratch of rank_grouping_block_counts_bytes
+size_t rank_grouping_block_counts_bytes(int64_t n_tokens, int n_experts, int top_k);
+hipError_t launch_rank_grouping(const int32_t *expert_idx, int64_t n_tokens, int n_experts, int top_k,
+                                int32_t *block_counts, int32_t *rank_offsets, int32_t *tok_of_rank_pos,
+                                hipStream_t s);
+
 // load-balance statistics (Eq. (16)); partial: f32 scratch of balance_scratch_bytes(E)
 size_t balance_scratch_bytes(int n_experts);
 hipError_t launch_balance_stats(const float *logits, const int32_t *counts, int64_t n_tokens,

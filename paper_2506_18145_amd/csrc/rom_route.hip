@@ -228,20 +228,26 @@ __device__ __forceinline__ unsigned long long match_expert(int key, int n_expert
   return mine;
 }
 
+// The three grouping kernels sort n_items keys; item s has the key expert_idx[s * stride + r] with
+// r = blockIdx.y (hist, scatter) or blockIdx.x (offsets).  stride 1, one rank: all N*K slots by
+// expert.  stride K, K ranks: for every rank r the N tokens by their r-th expert (the K > 1 path of
+// the layer runs a routed projection as K passes over the tokens, one per rank).  Per-rank arrays
+// follow one another: block_counts [rank][block][E], offsets [rank][E + 1] (each starting at 0),
+// tok_of_pos [rank][n_items].
 __global__ __launch_bounds__(kSortBlock) void hist_kernel(const int32_t *__restrict__ expert_idx,
-                                                          int64_t n_slots, int n_experts,
+                                                          int64_t n_items, int n_experts, int stride,
                                                           int32_t *__restrict__ block_counts) {
   __shared__ int cnt[kSortWaves][64];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t s = static_cast<int64_t>(blockIdx.x) * kSortBlock + threadIdx.x;
-  const int key = (s < n_slots) ? expert_idx[s] : -1;
+  const int key = (s < n_items) ? expert_idx[s * stride + blockIdx.y] : -1;
   match_expert(key, n_experts, lane, cnt[wave]);
   __syncthreads();
   if (threadIdx.x < n_experts) {
     int total = 0;
 #pragma unroll
     for (int w = 0; w < kSortWaves; ++w) total += cnt[w][threadIdx.x];
-    block_counts[static_cast<int64_t>(blockIdx.x) * n_experts + threadIdx.x] = total;
+    block_counts[(static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * n_experts + threadIdx.x] = total;
   }
 }
 
@@ -256,6 +262,9 @@ __global__ __launch_bounds__(kOffsetWaves *kWave) void offsets_kernel(int32_t *_
   __shared__ int total[64];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int n_waves = blockDim.x / kWave;
+  block_counts += static_cast<int64_t>(blockIdx.x) * n_blocks * n_experts;      // this rank's arrays
+  offsets += blockIdx.x * (n_experts + 1);
+  if (counts) counts += blockIdx.x * n_experts;
   for (int e = wave; e < n_experts; e += n_waves) {
     int run = 0;
     for (int64_t b0 = 0; b0 < n_blocks; b0 += kWave) {
@@ -272,7 +281,7 @@ __global__ __launch_bounds__(kOffsetWaves *kWave) void offsets_kernel(int32_t *_
     }
     if (lane == 0) {
       total[e] = run;
-      counts[e] = run;
+      if (counts) counts[e] = run;
     }
   }
   __syncthreads();
@@ -283,24 +292,26 @@ __global__ __launch_bounds__(kOffsetWaves *kWave) void offsets_kernel(int32_t *_
   }
 }
 
+// perm / inv_perm may be NULL (the per-rank groupings need the row map alone); tok_of_pos[pos] = s / tok_div
 __global__ __launch_bounds__(kSortBlock) void scatter_kernel(
-    const int32_t *__restrict__ expert_idx, int64_t n_slots, int n_experts, int top_k,
+    const int32_t *__restrict__ expert_idx, int64_t n_items, int n_experts, int stride, int tok_div,
     const int32_t *__restrict__ block_base, const int32_t *__restrict__ offsets,
     int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm, int32_t *__restrict__ tok_of_pos) {
   __shared__ int cnt[kSortWaves][64];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t s = static_cast<int64_t>(blockIdx.x) * kSortBlock + threadIdx.x;
-  const int key = (s < n_slots) ? expert_idx[s] : -1;
+  const int key = (s < n_items) ? expert_idx[s * stride + blockIdx.y] : -1;
   const unsigned long long same = match_expert(key, n_experts, lane, cnt[wave]);
   __syncthreads();
-  if (s >= n_slots || key < 0 || key >= n_experts) return;      // (a key outside [0, E) is never written by the router)
+  if (s >= n_items || key < 0 || key >= n_experts) return;      // (a key outside [0, E) is never written by the router)
   const unsigned long long below = same & ((1ull << lane) - 1ull);
-  int pos = offsets[key] + block_base[static_cast<int64_t>(blockIdx.x) * n_experts + key] +
+  offsets += blockIdx.y * (n_experts + 1);
+  int pos = offsets[key] + block_base[(static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * n_experts + key] +
             __popcll(below);
   for (int w = 0; w < wave; ++w) pos += cnt[w][key];
-  inv_perm[s] = pos;
-  perm[pos] = static_cast<int32_t>(s);
-  tok_of_pos[pos] = static_cast<int32_t>(s / top_k);
+  if (inv_perm) inv_perm[s] = pos;
+  if (perm) perm[pos] = static_cast<int32_t>(s);
+  tok_of_pos[static_cast<int64_t>(blockIdx.y) * n_items + pos] = static_cast<int32_t>(s / tok_div);
 }
 
 // Whole grouping in one workgroup for small slot counts (decode steps): three passes over the
@@ -512,13 +523,32 @@ hipError_t launch_permutation(const int32_t *expert_idx, int64_t n_slots, int n_
   }
   const int64_t blocks = route_blocks(n_slots);
   hipLaunchKernelGGL(hist_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kSortBlock), 0, s,
-                     expert_idx, n_slots, n_experts, block_counts);
+                     expert_idx, n_slots, n_experts, 1, block_counts);
   const int offset_waves = n_experts < kOffsetWaves ? n_experts : kOffsetWaves;
   hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(offset_waves * kWave), 0, s, block_counts, blocks, n_experts,
                      counts, offsets);
   hipLaunchKernelGGL(scatter_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kSortBlock), 0, s,
-                     expert_idx, n_slots, n_experts, top_k, block_counts, offsets, perm, inv_perm,
+                     expert_idx, n_slots, n_experts, 1, top_k, block_counts, offsets, perm, inv_perm,
                      tok_of_pos);
+  return hipGetLastError();
+}
+
+size_t rank_grouping_block_counts_bytes(int64_t n_tokens, int n_experts, int top_k) {
+  return static_cast<size_t>(top_k) * route_blocks(n_tokens) * n_experts * sizeof(int32_t);
+}
+
+hipError_t launch_rank_grouping(const int32_t *expert_idx, int64_t n_tokens, int n_experts, int top_k,
+                                int32_t *block_counts, int32_t *rank_offsets, int32_t *tok_of_rank_pos,
+                                hipStream_t s) {
+  const int64_t blocks = route_blocks(n_tokens);
+  const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(top_k));
+  hipLaunchKernelGGL(hist_kernel, grid, dim3(kSortBlock), 0, s, expert_idx, n_tokens, n_experts, top_k, block_counts);
+  const int offset_waves = n_experts < kOffsetWaves ? n_experts : kOffsetWaves;
+  hipLaunchKernelGGL(offsets_kernel, dim3(static_cast<unsigned>(top_k)), dim3(offset_waves * kWave), 0, s, block_counts,
+                     blocks, n_experts, static_cast<int32_t *>(nullptr), rank_offsets);
+  hipLaunchKernelGGL(scatter_kernel, grid, dim3(kSortBlock), 0, s, expert_idx, n_tokens, n_experts, top_k, 1,
+                     block_counts, rank_offsets, static_cast<int32_t *>(nullptr), static_cast<int32_t *>(nullptr),
+                     tok_of_rank_pos);
   return hipGetLastError();
 }
 

@@ -64,6 +64,13 @@ def test_small_layers(kw):
     # big tiles with a ragged last column tile (N = 2112), and an inner dimension that is not a
     # multiple of the 64-wide slab (d_inner = 1056: K-tail path of the register-staged 256x256 kernel)
     dict(batch=1, seq_len=4200, d_model=512, d_inner=1056, dt_rank=48, cfg_id=64),
+    # top-2 on >= 2048 tokens: the routed dt projection runs as two passes over the tokens (the second
+    # adds the first one's output, then bias + softplus), dt_rank 32 and 128; shared x/dt has nothing
+    # to pass over, and dt_rank 48 has no accumulating kernel and keeps the per-slot path
+    dict(batch=1, seq_len=3000, d_model=256, d_inner=512, dt_rank=32, n_experts=6, top_k=2, gate_mode=0, cfg_id=65),
+    dict(batch=3, seq_len=900, d_model=256, d_inner=512, dt_rank=128, top_k=2, gate_mode=1, cfg_id=66),
+    dict(batch=1, seq_len=2500, d_model=256, d_inner=512, dt_rank=16, top_k=2, gate_mode=1, routed_xdt=False, cfg_id=67),
+    dict(batch=1, seq_len=2100, d_model=256, d_inner=512, dt_rank=48, top_k=2, gate_mode=1, cfg_id=68),
 ])
 def test_medium_layers_big_tile_kernels(kw):
     cfg = small_cfg(**kw)
