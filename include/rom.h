@@ -197,7 +197,10 @@ ROM_API int rom_step_static(const rom_dims *dims, const rom_weights *w, const vo
  * gradient, the router is trained through the gate weights R_i of Eq. (12) (no jitter, no SparseMixer
  * estimator: the paper names those as options of its training runs only).  Zero initial conv / scan
  * states, no state gradient.
- * This build supports top_k == 1 (all of the paper's models); top_k > 1 returns ROM_E_UNSUPPORTED.
+ * Any top_k the forward pass takes: with top_k > 1 every selected expert's projection receives the
+ * token's gradient (Eq. (10)/(11) are indicator sums), the out projection's is weighted by the
+ * slot's gate, and the gate's own gradient is d_out against that expert's output.
+ * At most 2^24 (token, k) slots per call.
  * All gradient buffers are f32 device memory of the parameter's shape, written (not accumulated):
  * d_A_log is with respect to A_log.  d_b_router and d_conv_b may be NULL. */
 typedef struct rom_grads {

@@ -493,7 +493,7 @@ class RomLayer:
         B, L, _ = x.shape
         need = rom_backward_workspace_bytes(self.dims, max(B, 1), max(L, 1))
         if need == 0:
-            raise RomError("rom_backward_workspace_bytes returned 0: unsupported dims (top_k must be 1)")
+            raise RomError("rom_backward_workspace_bytes returned 0: unsupported dims")
         if self._bwd_ws is None or self._bwd_ws.numel() < need:
             self._bwd_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         d_x = torch.empty_like(x)

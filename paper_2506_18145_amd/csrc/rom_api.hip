@@ -461,6 +461,10 @@ FfnPlan make_ffn_plan(const rom_dims *d, int32_t d_ff, int64_t n_tok) {
 struct BwdPlan {              // byte offsets behind the forward plan
   size_t total, fwd_out, wt_out, wt_dt, wt_x, wt_in, dg_raw, d_gate, d_logits, d_pre, d_u_scan, d_xz, ckpt, bc_part,
       d_bc, d_dt_low, d_xdbl, d_u_x, dx_in, conv_part, router_part;
+  // top-K: per-position (sorted slot) staging of the routed input gradients, summed over a token's K
+  // slots afterwards like the forward's per-slot outputs: T [S, d_model] (gate-scaled d_out, then
+  // d x), T [S, d_inner] (d g, then d u), f32 [S, dt_rank] (d dt_low)
+  size_t pos_dm, pos_de, pos_r;
 };
 
 BwdPlan make_bwd_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
@@ -474,13 +478,14 @@ BwdPlan make_bwd_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   const size_t N = static_cast<size_t>(n_seq) * seq_len, E = d->n_experts, Ex = d->n_experts_xdt;
   const size_t b = d->dtype == ROM_DTYPE_BF16 ? 2 : 4;
   const size_t De = d->d_inner, Dm = d->d_model, R = d->dt_rank;
+  const size_t K = d->top_k, S = N * K;
   p.fwd_out = take(N * Dm * b);
   p.wt_out = take(E * Dm * De * b);
   p.wt_dt = take(Ex * De * R * b);
   p.wt_x = take(Ex * (R + 32) * De * b);
   p.wt_in = take(E * 2 * De * Dm * b);
   p.dg_raw = take(N * De * b);
-  p.d_gate = take(N * 4);
+  p.d_gate = take(S * 4);
   p.d_logits = take(N * E * 4);
   p.d_pre = take(N * De * b);
   p.d_u_scan = take(N * De * b);
@@ -494,6 +499,9 @@ BwdPlan make_bwd_plan(const rom_dims *d, int64_t n_seq, int64_t seq_len) {
   p.dx_in = take(N * Dm * b);
   p.conv_part = take(conv_bwd_partial_bytes(n_seq, seq_len, d->d_inner));
   p.router_part = take(router_bwd_partial_bytes(static_cast<int64_t>(N), d->d_model, d->n_experts));
+  p.pos_dm = K > 1 ? take(S * Dm * b) : kNone;
+  p.pos_de = K > 1 ? take(S * De * b) : kNone;
+  p.pos_r = (K > 1 && Ex > 1) ? take(S * R * 4) : kNone;
   p.total = off;
   return p;
 }
@@ -845,7 +853,7 @@ int rom_step_static(const rom_dims *dims, const rom_weights *w, const void *x, i
 }
 
 size_t rom_backward_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L) {
-  if (check_dims(dims) != ROM_OK || B < 0 || L < 0 || dims->top_k != 1) return 0;
+  if (check_dims(dims) != ROM_OK || B < 0 || L < 0) return 0;
   return make_bwd_plan(dims, B > 0 ? B : 1, L > 0 ? L : 1).total;
 }
 
@@ -855,7 +863,6 @@ int rom_layer_backward(const rom_dims *d, const rom_weights *w, const void *x, i
   if (rc != ROM_OK) return rc;
   rc = check_weights(d, w);
   if (rc != ROM_OK) return rc;
-  if (d->top_k != 1) return ROM_E_UNSUPPORTED;
   if (B < 0 || L < 0) return ROM_E_INVAL;
   if (B == 0 || L == 0) return ROM_OK;
   if (!x || !d_out || !d_x || !gr || !ws || d_x == x || d_x == d_out) return ROM_E_INVAL;
@@ -865,7 +872,7 @@ int rom_layer_backward(const rom_dims *d, const rom_weights *w, const void *x, i
                          gr->d_D, gr->d_w_out};
   for (const float *ptr : need)
     if (!ptr || !aligned16(ptr)) return ROM_E_INVAL;
-  if (B * L > (1ll << 24) || B > 65535) return ROM_E_UNSUPPORTED;      // grid limits of the reduction kernels
+  if (B * L * d->top_k > (1ll << 24) || B > 65535) return ROM_E_UNSUPPORTED;      // grid limits of the reduction kernels
   const BwdPlan bp = make_bwd_plan(d, B, L);
   if (ws_bytes < bp.total) return ROM_E_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -873,16 +880,19 @@ int rom_layer_backward(const rom_dims *d, const rom_weights *w, const void *x, i
   auto at = [&](size_t off) { return base + off; };
   const Plan p = make_plan(d, B, L);
   const int64_t N = B * L;
-  const int E = d->n_experts, Ex = d->n_experts_xdt, De = d->d_inner, Dm = d->d_model, R = d->dt_rank;
+  const int E = d->n_experts, Ex = d->n_experts_xdt, De = d->d_inner, Dm = d->d_model, R = d->dt_rank, K = d->top_k;
   const size_t eb = d->dtype == ROM_DTYPE_BF16 ? 2 : 4;
-  const bool routed_xdt = Ex > 1;
+  const bool routed_xdt = Ex > 1, multi = K > 1;
+  const int64_t S = N * K;
 
   // activations: the forward pass into the front part of the workspace
   rc = forward_impl(d, w, x, B, L, nullptr, nullptr, at(bp.fwd_out), nullptr, nullptr, ws, p.total, s);
   if (rc != ROM_OK) return rc;
   const int32_t *offsets = reinterpret_cast<const int32_t *>(at(p.offsets));
   const int32_t *tok_of_pos = reinterpret_cast<const int32_t *>(at(p.tok_of_pos));
-  const float *gate = reinterpret_cast<const float *>(at(p.gate));                 // [N] at top-1
+  const int32_t *perm = reinterpret_cast<const int32_t *>(at(p.perm));
+  const int32_t *inv_perm = reinterpret_cast<const int32_t *>(at(p.inv_perm));
+  const float *gate = reinterpret_cast<const float *>(at(p.gate));                 // [N, K]
   float *d_gate = reinterpret_cast<float *>(at(bp.d_gate));
   float *d_logits = reinterpret_cast<float *>(at(bp.d_logits));
 
@@ -892,59 +902,100 @@ int rom_layer_backward(const rom_dims *d, const rom_weights *w, const void *x, i
   ROM_TRY(launch_transpose(d->dtype, w->w_x, at(bp.wt_x), Ex, R + 32, De, s));         // -> [Ex][De][R+32]
   ROM_TRY(launch_transpose(d->dtype, w->w_in, at(bp.wt_in), E, 2 * De, Dm, s));        // -> [E][Dm][2De]
 
-  auto dgrad = [&](const void *A, int64_t lda, const void *Wt, int n_groups, int n_out, int k_in, void *C, int64_t ldc,
-                   int c_is_f32) {
+  // Input gradient of a routed projection, d_inp[n] = sum_k W[e_k(n)]^T d_outp[n]: the forward's grouped
+  // GEMM on the transposed weights.  top-1: rows gathered from and scattered to token order, C is the
+  // result.  top-K: A rows by token (or, a_by_pos, already one per sorted position), one output row per
+  // sorted position in `pos`, then the K rows of a token are added (like the forward's per-slot outputs).
+  auto dgrad = [&](const void *A, int64_t lda, bool a_by_pos, const void *Wt, int n_groups, int n_out, int k_in, void *C,
+                   int64_t ldc, int c_is_f32, void *pos) -> int {
     GemmArgs ga;
     memset(&ga, 0, sizeof(ga));
     ga.dtype = d->dtype;
-    ga.A = A; ga.lda = lda; ga.a_span = N * lda;
+    ga.A = A; ga.lda = lda; ga.a_span = (a_by_pos ? S : N) * lda;
     ga.W = Wt; ga.N = n_out; ga.K = k_in;
-    ga.C = C; ga.ldc = ldc; ga.c_is_f32 = c_is_f32;
-    ga.M = N;
-    if (n_groups > 1) {
-      ga.n_groups = n_groups; ga.offsets = offsets; ga.a_rows = tok_of_pos; ga.c_rows = tok_of_pos;
-    } else {
-      ga.n_groups = 1;
+    ga.ldc = ldc; ga.c_is_f32 = c_is_f32;
+    if (n_groups <= 1) {
+      ga.n_groups = 1; ga.M = N; ga.C = C;
+      ROM_TRY(launch_grouped_gemm(ga, s));
+      return ROM_OK;
     }
-    return launch_grouped_gemm(ga, s);
+    ga.n_groups = n_groups; ga.offsets = offsets; ga.M = S;
+    ga.a_rows = a_by_pos ? nullptr : tok_of_pos;
+    if (!multi) {
+      ga.c_rows = tok_of_pos; ga.C = C;
+      ROM_TRY(launch_grouped_gemm(ga, s));
+      return ROM_OK;
+    }
+    ga.C = pos;
+    ROM_TRY(launch_grouped_gemm(ga, s));
+    const bool f32 = c_is_f32 || eb == 4;
+    ROM_TRY(launch_slot_sum(f32, f32, pos, ldc, C, ldc, inv_perm, N, K, n_out, nullptr, 0, nullptr, s));
+    return ROM_OK;
   };
-  auto wgrad = [&](const void *A, int64_t lda, int M, const void *Bm, int64_t ldb, int Nn, int n_groups,
-                   const float *scale, float *C) {
-    return launch_wgrad(d->dtype, A, lda, M, Bm, ldb, Nn, n_groups > 1 ? tok_of_pos : nullptr, scale,
-                        n_groups > 1 ? offsets : nullptr, n_groups, N, C, s);
+  // Weight gradient d W[e] = sum over the expert's sorted positions of d_outp^T inp; both operands by
+  // the position's token unless a_by_pos says that A already has one row per position
+  auto wgrad = [&](const void *A, int64_t lda, bool a_by_pos, int M, const void *Bm, int64_t ldb, int Nn, int n_groups,
+                   float *C) {
+    const bool routed_call = n_groups > 1;
+    return launch_wgrad(d->dtype, A, lda, M, Bm, ldb, Nn, (routed_call && !a_by_pos) ? tok_of_pos : nullptr,
+                        routed_call ? tok_of_pos : nullptr, nullptr, routed_call ? offsets : nullptr, n_groups,
+                        routed_call ? S : N, C, s);
   };
+#define ROM_RC(expr)            \
+  do {                          \
+    const int rc_ = (expr);     \
+    if (rc_ != ROM_OK) return rc_; \
+  } while (0)
 
-  // Eq. (12)/(13): out = gate * (W_out[e] g)
-  ROM_TRY(dgrad(d_out, Dm, at(bp.wt_out), E, De, Dm, at(bp.dg_raw), De, 0));           // dg_raw = W_out[e]^T d_out
-  ROM_TRY(launch_gate_backward(d->dtype, at(bp.dg_raw), at(p.g), N, De, d_gate, s));
-  // (the gate weight goes onto d_out once, in the buffer that later receives dx_in, so that the
-  // weight-gradient kernel contracts two plain operands)
-  ROM_TRY(launch_scale_rows(d->dtype, d_out, gate, N, Dm, at(bp.dx_in), s));
-  ROM_TRY(wgrad(at(bp.dx_in), Dm, Dm, at(p.g), De, De, E, nullptr, gr->d_w_out));
+  // Eq. (12)/(13): out = sum_k gate_k * (W_out[e_k] g)
+  const void *dsc;            // gate-weighted d_out, one row per sorted position
+  const float *scan_gate;     // weight the adjoint scan still has to put on d g
+  if (!multi) {
+    ROM_RC(dgrad(d_out, Dm, false, at(bp.wt_out), E, De, Dm, at(bp.dg_raw), De, 0, nullptr));   // dg_raw = W_out[e]^T d_out
+    ROM_TRY(launch_gate_backward(d->dtype, at(bp.dg_raw), at(p.g), nullptr, 1, N, De, d_gate, s));
+    // (the gate weight goes onto d_out once, in the buffer that later receives dx_in, so that the
+    // weight-gradient kernel contracts two plain operands)
+    ROM_TRY(launch_scale_rows(d->dtype, d_out, gate, nullptr, nullptr, N, Dm, at(bp.dx_in), s));
+    ROM_TRY(wgrad(at(bp.dx_in), Dm, false, Dm, at(p.g), De, De, E, gr->d_w_out));
+    scan_gate = gate;
+  } else {
+    // d gate of a slot: d_out of its token against the expert output the forward pass left per position
+    ROM_TRY(launch_gate_backward(d->dtype, d_out, at(p.op_sorted), inv_perm, K, S, Dm, d_gate, s));
+    ROM_TRY(launch_scale_rows(d->dtype, d_out, gate, tok_of_pos, perm, S, Dm, at(bp.pos_dm), s));
+    dsc = at(bp.pos_dm);
+    ROM_TRY(wgrad(dsc, Dm, true, Dm, at(p.g), De, De, E, gr->d_w_out));
+    ROM_RC(dgrad(dsc, Dm, true, at(bp.wt_out), E, De, Dm, at(bp.dg_raw), De, 0, at(bp.pos_de)));   // already gate-weighted
+    scan_gate = nullptr;
+  }
   // Eq. (5), (6): scan, gate, softplus
   ROM_TRY(launch_scan_backward(d->dtype, at(p.u), at(p.dt), reinterpret_cast<const float *>(at(p.bc)),
-                               at(p.xz) + static_cast<size_t>(De) * eb, 2 * De, at(bp.dg_raw), gate, w->A_log, w->D, B, L,
-                               De, reinterpret_cast<float *>(at(bp.ckpt)), reinterpret_cast<float *>(at(bp.bc_part)),
-                               at(bp.d_pre), at(bp.d_u_scan), at(bp.d_xz) + static_cast<size_t>(De) * eb, 2 * De,
-                               reinterpret_cast<float *>(at(bp.d_bc)), gr->d_A_log, gr->d_D, gr->d_dt_bias, s));
+                               at(p.xz) + static_cast<size_t>(De) * eb, 2 * De, at(bp.dg_raw), scan_gate, w->A_log, w->D,
+                               B, L, De, reinterpret_cast<float *>(at(bp.ckpt)),
+                               reinterpret_cast<float *>(at(bp.bc_part)), at(bp.d_pre), at(bp.d_u_scan),
+                               at(bp.d_xz) + static_cast<size_t>(De) * eb, 2 * De, reinterpret_cast<float *>(at(bp.d_bc)),
+                               gr->d_A_log, gr->d_D, gr->d_dt_bias, s));
   // dt projection
-  ROM_TRY(dgrad(at(bp.d_pre), De, at(bp.wt_dt), routed_xdt ? E : 1, R, De, at(bp.d_dt_low), R, 1));
-  ROM_TRY(wgrad(at(bp.d_pre), De, De, at(p.dt_low), R, R, routed_xdt ? E : 1, nullptr, gr->d_w_dt));
+  ROM_RC(dgrad(at(bp.d_pre), De, false, at(bp.wt_dt), routed_xdt ? E : 1, R, De, at(bp.d_dt_low), R, 1,
+               multi && routed_xdt ? at(bp.pos_r) : nullptr));
+  ROM_TRY(wgrad(at(bp.d_pre), De, false, De, at(p.dt_low), R, R, routed_xdt ? E : 1, gr->d_w_dt));
   // x projection
   ROM_TRY(launch_pack_dxdbl(d->dtype, reinterpret_cast<const float *>(at(bp.d_dt_low)),
                             reinterpret_cast<const float *>(at(bp.d_bc)), N, R, at(bp.d_xdbl), s));
-  ROM_TRY(dgrad(at(bp.d_xdbl), R + 32, at(bp.wt_x), routed_xdt ? E : 1, De, R + 32, at(bp.d_u_x), De, 0));
-  ROM_TRY(wgrad(at(bp.d_xdbl), R + 32, R + 32, at(p.u), De, De, routed_xdt ? E : 1, nullptr, gr->d_w_x));
+  ROM_RC(dgrad(at(bp.d_xdbl), R + 32, false, at(bp.wt_x), routed_xdt ? E : 1, De, R + 32, at(bp.d_u_x), De, 0,
+               multi ? at(bp.pos_de) : nullptr));
+  ROM_TRY(wgrad(at(bp.d_xdbl), R + 32, false, R + 32, at(p.u), De, De, routed_xdt ? E : 1, gr->d_w_x));
   // Eq. (2): conv + SiLU; writes the conv half of d_xz
   ROM_TRY(launch_conv_backward(d->dtype, at(p.xz), 2 * De, w->conv_w, w->conv_b, at(bp.d_u_scan), at(bp.d_u_x), B, L, De,
                                at(bp.d_xz), 2 * De, reinterpret_cast<float *>(at(bp.conv_part)), gr->d_conv_w,
                                gr->d_conv_b, s));
   // Eq. (10)/(11): in / gate projection
-  ROM_TRY(dgrad(at(bp.d_xz), 2 * De, at(bp.wt_in), E, Dm, 2 * De, at(bp.dx_in), Dm, 0));
-  ROM_TRY(wgrad(at(bp.d_xz), 2 * De, 2 * De, x, Dm, Dm, E, nullptr, gr->d_w_in));
+  ROM_RC(dgrad(at(bp.d_xz), 2 * De, false, at(bp.wt_in), E, Dm, 2 * De, at(bp.dx_in), Dm, 0,
+               multi ? at(bp.pos_dm) : nullptr));
+  ROM_TRY(wgrad(at(bp.d_xz), 2 * De, false, 2 * De, x, Dm, Dm, E, gr->d_w_in));
+#undef ROM_RC
   // Eq. (9): the router through the gate weights
   ROM_TRY(launch_router_backward(d->dtype, reinterpret_cast<const float *>(at(p.logits)),
-                                 reinterpret_cast<const int32_t *>(at(p.expert_idx)), d_gate, x, N, Dm, E, 1,
+                                 reinterpret_cast<const int32_t *>(at(p.expert_idx)), d_gate, x, N, Dm, E, K,
                                  d->gate_mode, d_logits, reinterpret_cast<float *>(at(bp.router_part)), gr->d_w_router,
                                  gr->d_b_router, s));
   ROM_TRY(launch_dx_finish(d->dtype, at(bp.dx_in), d_logits, w->w_router, N, Dm, E, d_x, s));

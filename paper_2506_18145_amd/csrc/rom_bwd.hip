@@ -440,20 +440,23 @@ __global__ __launch_bounds__(256) void bwd_reduce_bc_kernel(const float *__restr
 }
 
 // ------------------------------------------------------------------ gate weights, Eq. (9)/(12)
+// d_gate[r] = a[ia(r), :] . b[ib(r), :], one wavefront per row r.
 // top-1: d_gate[n] = d_out[n, :] . (W_out[e_n] g[n, :]) = (W_out[e_n]^T d_out[n, :]) . g[n, :] = dg_raw[n, :] . g[n, :]
-// one wavefront per token
+// (both in token order, no maps).  top-K: r is a slot, a = d_out by the slot's token (r / K), b = the
+// expert output W_out[e] g that the forward pass left per sorted position (row inv_perm[r]).
 template <typename T>
-__global__ __launch_bounds__(256) void gate_bwd_kernel(const T *__restrict__ dg_raw, const T *__restrict__ g,
-                                                       int64_t n_tok, int d_inner, float *__restrict__ d_gate) {
+__global__ __launch_bounds__(256) void gate_bwd_kernel(const T *__restrict__ a, const T *__restrict__ b,
+                                                       const int32_t *__restrict__ b_rows, int a_div, int64_t n_rows,
+                                                       int n_cols, float *__restrict__ d_gate) {
   const int lane = threadIdx.x & 63;
-  const int64_t n = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) >> 6;
-  if (n >= n_tok) return;
+  const int64_t r = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) >> 6;
+  if (r >= n_rows) return;
+  const int64_t ra = r / a_div, rb = b_rows ? b_rows[r] : r;
   float acc = 0.0f;
-  for (int c = lane; c < d_inner; c += 64)
-    acc = fmaf(to_f32(dg_raw[n * d_inner + c]), to_f32(g[n * d_inner + c]), acc);
+  for (int c = lane; c < n_cols; c += 64) acc = fmaf(to_f32(a[ra * n_cols + c]), to_f32(b[rb * n_cols + c]), acc);
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) acc += __shfl_xor(acc, o, 64);
-  if (lane == 0) d_gate[n] = acc;
+  if (lane == 0) d_gate[r] = acc;
 }
 
 // d_logits [N, E] from d_gate [N, K]: softmax over all E experts, gate = P of the selected
@@ -684,7 +687,8 @@ __device__ __forceinline__ void wgrad_park8x8(const u32x4_t (&v)[8], bf16_t (*ds
 
 __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const bf16_t *__restrict__ A, int64_t lda, int M,
                                                          const bf16_t *__restrict__ Bm, int64_t ldb, int N,
-                                                         const int32_t *__restrict__ rows,
+                                                         const int32_t *__restrict__ rows_a,
+                                                         const int32_t *__restrict__ rows_b,
                                                          const int32_t *__restrict__ offsets, int64_t n_pos,
                                                          float *__restrict__ C) {
   __shared__ __attribute__((aligned(16))) bf16_t As[kWgTile][kWgPitch];
@@ -707,6 +711,7 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const bf16_t *__restric
   const bool is_a = tid < 128;
   const int t2 = tid & 127, pg = t2 & 7, piece = t2 >> 3;       // 16 consecutive lanes park into 64 distinct banks
   const bf16_t *src = is_a ? A : Bm;
+  const int32_t *rows = is_a ? rows_a : rows_b;      // position -> row of this operand (NULL: the position itself)
   const int64_t ld = is_a ? lda : ldb;
   const int col = (is_a ? m0 : n0) + piece * 8;
   const bool col_ok = col < (is_a ? M : N);
@@ -762,20 +767,27 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const bf16_t *__restric
   }
 }
 
-// rows scaled by a per-row factor: dst[n, :] = scale[n] * src[n, :] (the gate weight of Eq. (12) on d_out)
+// rows scaled by a per-row factor (the gate weight of Eq. (12) on d_out):
+// dst[r, :] = scale[scale_idx ? scale_idx[r] : r] * src[src_idx ? src_idx[r] : r, :]
+// (top-K: r is a sorted position, src_idx its token, scale_idx its slot)
 template <typename T>
 __global__ __launch_bounds__(256) void scale_rows_kernel(const T *__restrict__ src, const float *__restrict__ scale,
-                                                         int64_t n_rows, int n_cols, T *__restrict__ dst) {
+                                                         const int32_t *__restrict__ src_idx,
+                                                         const int32_t *__restrict__ scale_idx, int64_t n_rows,
+                                                         int n_cols, T *__restrict__ dst) {
   const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
   if (i >= n_rows * n_cols) return;
-  dst[i] = from_f32<T>(to_f32(src[i]) * scale[i / n_cols]);
+  const int64_t r = i / n_cols, c = i % n_cols;
+  const int64_t rs = src_idx ? src_idx[r] : r, rg = scale_idx ? scale_idx[r] : r;
+  dst[i] = from_f32<T>(to_f32(src[rs * n_cols + c]) * scale[rg]);
 }
 
 // the same contraction on the plain ALUs (fp32, or bf16 shapes the MFMA kernel does not take): 64 x 64 tiles
 template <typename T>
 __global__ __launch_bounds__(256) void wgrad_simple_kernel(const T *__restrict__ A, int64_t lda, int M,
                                                            const T *__restrict__ Bm, int64_t ldb, int N,
-                                                           const int32_t *__restrict__ rows,
+                                                           const int32_t *__restrict__ rows_a,
+                                                           const int32_t *__restrict__ rows_b,
                                                            const float *__restrict__ row_scale,
                                                            const int32_t *__restrict__ offsets, int64_t n_pos,
                                                            float *__restrict__ C) {
@@ -792,10 +804,10 @@ __global__ __launch_bounds__(256) void wgrad_simple_kernel(const T *__restrict__
       const int64_t p = p0 + pp;
       float va = 0.0f, vb = 0.0f;
       if (p < p_hi) {
-        const int64_t r = rows ? rows[p] : p;
-        const float sc = row_scale ? row_scale[r] : 1.0f;
-        if (m0 + c < M) va = to_f32(A[r * lda + m0 + c]) * sc;
-        if (n0 + c < N) vb = to_f32(Bm[r * ldb + n0 + c]);
+        const int64_t ra = rows_a ? rows_a[p] : p, rb = rows_b ? rows_b[p] : p;
+        const float sc = row_scale ? row_scale[ra] : 1.0f;
+        if (m0 + c < M) va = to_f32(A[ra * lda + m0 + c]) * sc;
+        if (n0 + c < N) vb = to_f32(Bm[rb * ldb + n0 + c]);
       }
       As[pp][c] = va;
       Bs[pp][c] = vb;
@@ -877,15 +889,15 @@ hipError_t launch_scan_backward(int dtype, const void *u, const void *dt, const 
   return hipGetLastError();
 }
 
-hipError_t launch_gate_backward(int dtype, const void *dg_raw, const void *g, int64_t n_tok, int d_inner, float *d_gate,
-                                hipStream_t s) {
-  const dim3 grid = grid1d(n_tok * 64, 256);
+hipError_t launch_gate_backward(int dtype, const void *a, const void *b, const int32_t *b_rows, int a_div,
+                                int64_t n_rows, int n_cols, float *d_gate, hipStream_t s) {
+  const dim3 grid = grid1d(n_rows * 64, 256);
   if (dtype == ROM_DTYPE_BF16)
-    hipLaunchKernelGGL((gate_bwd_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(dg_raw),
-                       static_cast<const bf16_t *>(g), n_tok, d_inner, d_gate);
+    hipLaunchKernelGGL((gate_bwd_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(a),
+                       static_cast<const bf16_t *>(b), b_rows, a_div, n_rows, n_cols, d_gate);
   else
-    hipLaunchKernelGGL((gate_bwd_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(dg_raw),
-                       static_cast<const float *>(g), n_tok, d_inner, d_gate);
+    hipLaunchKernelGGL((gate_bwd_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(a),
+                       static_cast<const float *>(b), b_rows, a_div, n_rows, n_cols, d_gate);
   return hipGetLastError();
 }
 
@@ -972,38 +984,38 @@ hipError_t launch_pack_dxdbl(int dtype, const float *d_dt_low, const float *d_bc
   return hipGetLastError();
 }
 
-hipError_t launch_scale_rows(int dtype, const void *src, const float *scale, int64_t n_rows, int n_cols, void *dst,
-                             hipStream_t s) {
+hipError_t launch_scale_rows(int dtype, const void *src, const float *scale, const int32_t *src_idx,
+                             const int32_t *scale_idx, int64_t n_rows, int n_cols, void *dst, hipStream_t s) {
   const dim3 grid = grid1d(n_rows * n_cols, 256);
   if (dtype == ROM_DTYPE_BF16)
-    hipLaunchKernelGGL((scale_rows_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(src), scale, n_rows,
-                       n_cols, static_cast<bf16_t *>(dst));
+    hipLaunchKernelGGL((scale_rows_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(src), scale,
+                       src_idx, scale_idx, n_rows, n_cols, static_cast<bf16_t *>(dst));
   else
-    hipLaunchKernelGGL((scale_rows_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(src), scale, n_rows,
-                       n_cols, static_cast<float *>(dst));
+    hipLaunchKernelGGL((scale_rows_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(src), scale,
+                       src_idx, scale_idx, n_rows, n_cols, static_cast<float *>(dst));
   return hipGetLastError();
 }
 
 hipError_t launch_wgrad(int dtype, const void *A, int64_t lda, int M, const void *Bm, int64_t ldb, int N,
-                        const int32_t *rows, const float *row_scale, const int32_t *offsets, int n_groups,
-                        int64_t n_pos, float *C, hipStream_t s) {
+                        const int32_t *rows_a, const int32_t *rows_b, const float *row_scale, const int32_t *offsets,
+                        int n_groups, int64_t n_pos, float *C, hipStream_t s) {
   const bool mfma = dtype == ROM_DTYPE_BF16 && M % 8 == 0 && N % 8 == 0 && lda % 8 == 0 && ldb % 8 == 0 &&
                     reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(Bm) % 16 == 0;
   if (mfma && !row_scale) {
     const dim3 grid(static_cast<unsigned>(ceil_div(N, kWgTile)), static_cast<unsigned>(ceil_div(M, kWgTile)),
                     static_cast<unsigned>(n_groups));
     hipLaunchKernelGGL(wgrad_bf16_kernel, grid, dim3(256), 0, s, static_cast<const bf16_t *>(A), lda, M,
-                       static_cast<const bf16_t *>(Bm), ldb, N, rows, offsets, n_pos, C);
+                       static_cast<const bf16_t *>(Bm), ldb, N, rows_a, rows_b, offsets, n_pos, C);
     return hipGetLastError();
   }
   const dim3 grid(static_cast<unsigned>(ceil_div(N, 64)), static_cast<unsigned>(ceil_div(M, 64)),
                   static_cast<unsigned>(n_groups));
   if (dtype == ROM_DTYPE_BF16)
     hipLaunchKernelGGL((wgrad_simple_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(A), lda, M,
-                       static_cast<const bf16_t *>(Bm), ldb, N, rows, row_scale, offsets, n_pos, C);
+                       static_cast<const bf16_t *>(Bm), ldb, N, rows_a, rows_b, row_scale, offsets, n_pos, C);
   else
     hipLaunchKernelGGL((wgrad_simple_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(A), lda, M,
-                       static_cast<const float *>(Bm), ldb, N, rows, row_scale, offsets, n_pos, C);
+                       static_cast<const float *>(Bm), ldb, N, rows_a, rows_b, row_scale, offsets, n_pos, C);
   return hipGetLastError();
 }
 

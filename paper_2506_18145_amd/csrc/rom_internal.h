@@ -140,8 +140,9 @@ hipError_t launch_scan_backward(int dtype, const void *u, const void *dt, const 
                                 int64_t L, int d_inner, float *ckpt, float *d_bc_part, void *d_pre, void *d_u, void *d_z,
                                 int64_t ld_dz, float *d_bc, float *d_A_log, float *d_D, float *d_dt_bias,
                                 hipStream_t s);
-hipError_t launch_gate_backward(int dtype, const void *dg_raw, const void *g, int64_t n_tok, int d_inner, float *d_gate,
-                                hipStream_t s);
+// d_gate[r] = a[r / a_div, :] . b[b_rows ? b_rows[r] : r, :] over n_cols columns
+hipError_t launch_gate_backward(int dtype, const void *a, const void *b, const int32_t *b_rows, int a_div,
+                                int64_t n_rows, int n_cols, float *d_gate, hipStream_t s);
 size_t router_bwd_partial_bytes(int64_t n_tok, int d_model, int n_experts);
 hipError_t launch_router_backward(int dtype, const float *logits, const int32_t *expert_idx, const float *d_gate,
                                   const void *x, int64_t n_tok, int d_model, int n_experts, int top_k, int gate_mode,
@@ -156,13 +157,14 @@ hipError_t launch_conv_backward(int dtype, const void *xz, int64_t ld_xz, const 
 hipError_t launch_transpose(int dtype, const void *src, void *dst, int n_mats, int rows, int cols, hipStream_t s);
 hipError_t launch_pack_dxdbl(int dtype, const float *d_dt_low, const float *d_bc, int64_t n_tok, int dt_rank,
                              void *d_xdbl, hipStream_t s);
-hipError_t launch_scale_rows(int dtype, const void *src, const float *scale, int64_t n_rows, int n_cols, void *dst,
-                             hipStream_t s);
-// C[e][m][n] (f32) = sum over positions p in [offsets[e], offsets[e+1]) of scale[row(p)] * A[row(p)][m] * B[row(p)][n]
-// (rows NULL: row(p) = p; offsets NULL: one group over [0, n_pos); row_scale NULL: 1)
+// dst[r, :] = scale[scale_idx ? scale_idx[r] : r] * src[src_idx ? src_idx[r] : r, :]
+hipError_t launch_scale_rows(int dtype, const void *src, const float *scale, const int32_t *src_idx,
+                             const int32_t *scale_idx, int64_t n_rows, int n_cols, void *dst, hipStream_t s);
+// C[e][m][n] (f32) = sum over positions p in [offsets[e], offsets[e+1]) of scale[ra(p)] * A[ra(p)][m] * B[rb(p)][n]
+// (rows_a / rows_b NULL: the position itself; offsets NULL: one group over [0, n_pos); row_scale NULL: 1)
 hipError_t launch_wgrad(int dtype, const void *A, int64_t lda, int M, const void *Bm, int64_t ldb, int N,
-                        const int32_t *rows, const float *row_scale, const int32_t *offsets, int n_groups,
-                        int64_t n_pos, float *C, hipStream_t s);
+                        const int32_t *rows_a, const int32_t *rows_b, const float *row_scale, const int32_t *offsets,
+                        int n_groups, int64_t n_pos, float *C, hipStream_t s);
 
 // timing probes (bench.py --probe): out is f32 scratch of n_blocks * 256 floats
 hipError_t launch_probe_issue(int op, int chains, int n_blocks, int iters, float *out, hipStream_t s);

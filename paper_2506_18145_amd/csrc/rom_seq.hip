@@ -68,21 +68,22 @@ __global__ __launch_bounds__(256) void slot_sum_kernel(const TS *__restrict__ sr
                                                        const float *__restrict__ bias, int softplus,
                                                        const float *__restrict__ row_scale) {
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  const int pairs = n_cols / 2;
+  const int pairs = (n_cols + 1) / 2;
   if (idx >= n_tokens * pairs) return;
   const int64_t n = idx / pairs;
   const int c = static_cast<int>(idx % pairs) * 2;
+  const bool two = c + 1 < n_cols;            // an odd column count ends on a single column
   float a0 = 0.0f, a1 = 0.0f;
   for (int k = 0; k < top_k; ++k) {
     const int64_t row = inv_perm[n * top_k + k];
     a0 += to_f32(src[row * ld_src + c]);
-    a1 += to_f32(src[row * ld_src + c + 1]);
+    if (two) a1 += to_f32(src[row * ld_src + c + 1]);
   }
   if (row_scale) { a0 *= row_scale[n]; a1 *= row_scale[n]; }
-  if (bias) { a0 += bias[c]; a1 += bias[c + 1]; }
+  if (bias) { a0 += bias[c]; if (two) a1 += bias[c + 1]; }
   if (softplus) { a0 = softplus_f32(a0); a1 = softplus_f32(a1); }
   dst[n * ld_dst + c] = from_f32<TD>(a0);
-  dst[n * ld_dst + c + 1] = from_f32<TD>(a1);
+  if (two) dst[n * ld_dst + c + 1] = from_f32<TD>(a1);
 }
 
 // xdbl rows (f32, R + 32 columns) -> dt_low (T) and bc (f32); sums the K slots when inv_perm is given
@@ -1005,7 +1006,7 @@ hipError_t launch_slot_sum(int src_is_f32, int dst_is_f32, const void *src, int6
   const bool wide = n_cols % 8 == 0 && ld_src % 8 == 0 && ld_dst % 8 == 0 &&
                     reinterpret_cast<uintptr_t>(src) % 16 == 0 && reinterpret_cast<uintptr_t>(dst) % 16 == 0 &&
                     (!bias || reinterpret_cast<uintptr_t>(bias) % 16 == 0);
-  const dim3 grid = wide ? grid1d(n_tokens * (n_cols / 8), 256) : grid1d(n_tokens * (n_cols / 2), 256);
+  const dim3 grid = wide ? grid1d(n_tokens * (n_cols / 8), 256) : grid1d(n_tokens * ((n_cols + 1) / 2), 256);
 #define ROM_SS(TS, TD)                                                                            \
   do {                                                                                            \
     if (wide)                                                                                     \
