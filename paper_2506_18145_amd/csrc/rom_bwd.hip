@@ -499,7 +499,7 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(const float *__restrict
 
 // partial[chunk][e][d] = sum over the chunk's tokens of d_logits[n, e] * x[n, d]  (d = d_model is the
 // bias column: x = 1).  grid (ceil((d_model + 1) / 256), n_chunks); a thread owns one column.
-constexpr int kRouterChunk = 512;
+constexpr int kRouterChunk = 128;    // (512: 288 blocks on 256 CUs, one wavefront per SIMD walking 512 dependent rows: 0.24 ms at 16K tokens)
 template <typename T, int EMAX>
 __global__ __launch_bounds__(256) void router_wgrad_partial_kernel(const float *__restrict__ d_logits,
                                                                    const T *__restrict__ x, int64_t n_tok, int d_model,
@@ -546,18 +546,24 @@ __global__ __launch_bounds__(256) void router_wgrad_finish_kernel(const float *_
   else if (d_b_router) d_b_router[e] = tot;
 }
 
-// d_x[n, d] = dx_in[n, d] + sum_e d_logits[n, e] * W_r[e, d]
+// d_x[n, d] = dx_in[n, d] + sum_e d_logits[n, e] * W_r[e, d]; a thread owns four consecutive columns
 template <typename T>
 __global__ __launch_bounds__(256) void dx_finish_kernel(const T *__restrict__ dx_in, const float *__restrict__ d_logits,
                                                         const T *__restrict__ w_router, int64_t n_tok, int d_model,
                                                         int n_experts, T *__restrict__ d_x) {
-  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t i = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) * 4;
   if (i >= n_tok * d_model) return;
   const int64_t n = i / d_model;
   const int d = static_cast<int>(i % d_model);
-  float v = to_f32(dx_in[i]);
-  for (int e = 0; e < n_experts; ++e) v = fmaf(d_logits[n * n_experts + e], to_f32(w_router[e * d_model + d]), v);
-  d_x[i] = from_f32<T>(v);
+  float v[4], wv[4];
+  bwd_load4(dx_in + i, v);
+  for (int e = 0; e < n_experts; ++e) {
+    const float dl = d_logits[n * n_experts + e];
+    bwd_load4(w_router + static_cast<int64_t>(e) * d_model + d, wv);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) v[q] = fmaf(dl, wv[q], v[q]);
+  }
+  bwd_store4(d_x + i, v);
 }
 
 // ------------------------------------------------------------------ adjoint of conv + SiLU, Eq. (2)
@@ -585,26 +591,35 @@ __global__ __launch_bounds__(256) void conv_bwd_kernel(const T *__restrict__ xz,
   const T *xr = xz + b * L * ld_xz + ch;
   const int64_t tok0 = b * L;
   auto xin = [&](int64_t t) { return (t >= 0 && t < L) ? to_f32(xr[t * ld_xz]) : 0.0f; };
-  auto dc_at = [&](int64_t t) {            // d loss / d c_t (0 outside the sequence)
+  // d loss / d c_t (0 outside the sequence) from the four inputs x_{t-3..t} of c_t
+  auto dc_of = [&](int64_t t, float x0, float x1, float x2, float x3) {
     if (t < 0 || t >= L) return 0.0f;
-    const float c = bias + w[0] * xin(t - 3) + w[1] * xin(t - 2) + w[2] * xin(t - 1) + w[3] * xin(t);
+    const float c = bias + w[0] * x0 + w[1] * x1 + w[2] * x2 + w[3] * x3;
     const float sig = sigmoid_f32(c);
     const float du = to_f32(du_a[(tok0 + t) * d_inner + ch]) + to_f32(du_b[(tok0 + t) * d_inner + ch]);
     return du * sig * (1.0f + c * (1.0f - sig));
   };
   float acc_w[4] = {0.f, 0.f, 0.f, 0.f}, acc_b = 0.0f;
-  // d_c of t, t+1, t+2, t+3 slide along the run
-  float d0 = dc_at(t0), d1 = dc_at(t0 + 1), d2 = dc_at(t0 + 2);
+  // the inputs x_{t-3} .. x_{t+3} and d_c of t .. t+3 slide along the run: one new x row, one new pair
+  // of d u rows and one output row per step
+  float xs[7];
+#pragma unroll
+  for (int k = 0; k < 6; ++k) xs[k] = xin(t0 - 3 + k);
+  float d0 = dc_of(t0, xs[0], xs[1], xs[2], xs[3]), d1 = dc_of(t0 + 1, xs[1], xs[2], xs[3], xs[4]),
+        d2 = dc_of(t0 + 2, xs[2], xs[3], xs[4], xs[5]);
   for (int64_t t = t0; t < t1; ++t) {
-    const float d3 = dc_at(t + 3);
+    xs[6] = xin(t + 3);
+    const float d3 = dc_of(t + 3, xs[3], xs[4], xs[5], xs[6]);
     // x_t feeds c_t (tap 3), c_{t+1} (tap 2), c_{t+2} (tap 1), c_{t+3} (tap 0)
     d_xpre[(tok0 + t) * ld_dx + ch] = from_f32<T>(w[3] * d0 + w[2] * d1 + w[1] * d2 + w[0] * d3);
     acc_b += d0;
-    acc_w[0] = fmaf(d0, xin(t - 3), acc_w[0]);
-    acc_w[1] = fmaf(d0, xin(t - 2), acc_w[1]);
-    acc_w[2] = fmaf(d0, xin(t - 1), acc_w[2]);
-    acc_w[3] = fmaf(d0, xin(t), acc_w[3]);
+    acc_w[0] = fmaf(d0, xs[0], acc_w[0]);
+    acc_w[1] = fmaf(d0, xs[1], acc_w[1]);
+    acc_w[2] = fmaf(d0, xs[2], acc_w[2]);
+    acc_w[3] = fmaf(d0, xs[3], acc_w[3]);
     d0 = d1; d1 = d2; d2 = d3;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) xs[k] = xs[k + 1];
   }
   const int64_t n_runs = gridDim.y;
   float *dst = partial + ((b * n_runs + run) * 5) * d_inner + ch;
@@ -627,19 +642,44 @@ __global__ __launch_bounds__(256) void conv_bwd_finish_kernel(const float *__res
 
 // ------------------------------------------------------------------ weight transposes for the input gradients
 // dst[e][c][r] = src[e][r][c]: the grouped GEMM contracts over the contiguous index of both operands,
-// and d_inp = d_out W contracts over W's row index.  32 x 32 tiles through LDS.
+// and d_inp = d_out W contracts over W's row index.  64 x 64 tiles through LDS; when rows and cols
+// are multiples of 4, both the global reads and the global writes move four consecutive elements.
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ src, T *__restrict__ dst, int rows,
-                                                        int cols) {
-  __shared__ T tile[32][33];
+                                                        int cols, int vec) {
+  __shared__ float tile[64][65];
   const int64_t base = static_cast<int64_t>(blockIdx.z) * rows * cols;
-  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
-  for (int i = ty; i < 32; i += 8)
-    if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = src[base + static_cast<int64_t>(r0 + i) * cols + c0 + tx];
-  __syncthreads();
-  for (int i = ty; i < 32; i += 8)
-    if (c0 + i < cols && r0 + tx < rows) dst[base + static_cast<int64_t>(c0 + i) * rows + r0 + tx] = tile[tx][i];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  if (vec) {
+    // thread -> (row i = tid / 16 + 16 q, columns 4 (tid % 16) .. + 3)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int i = (threadIdx.x >> 4) + 16 * q, j = (threadIdx.x & 15) * 4;
+      float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (r0 + i < rows && c0 + j < cols) bwd_load4(src + base + static_cast<int64_t>(r0 + i) * cols + c0 + j, v);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) tile[i][j + e] = v[e];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int i = (threadIdx.x >> 4) + 16 * q, j = (threadIdx.x & 15) * 4;     // output row c0 + i, columns r0 + j ..
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = tile[j + e][i];
+      if (c0 + i < cols && r0 + j < rows) bwd_store4(dst + base + static_cast<int64_t>(c0 + i) * rows + r0 + j, v);
+    }
+  } else {
+    for (int k = threadIdx.x; k < 64 * 64; k += 256) {
+      const int i = k / 64, j = k % 64;
+      if (r0 + i < rows && c0 + j < cols) tile[i][j] = to_f32(src[base + static_cast<int64_t>(r0 + i) * cols + c0 + j]);
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < 64 * 64; k += 256) {
+      const int i = k / 64, j = k % 64;
+      if (c0 + i < cols && r0 + j < rows) dst[base + static_cast<int64_t>(c0 + i) * rows + r0 + j] = from_f32<T>(tile[j][i]);
+    }
+  }
 }
 
 // d_xdbl [N, R + 32] (type T) = [ d_dt_low (f32 [N, R]) | d_bc (f32 [N, 32]) ]
@@ -775,11 +815,16 @@ __global__ __launch_bounds__(256) void scale_rows_kernel(const T *__restrict__ s
                                                          const int32_t *__restrict__ src_idx,
                                                          const int32_t *__restrict__ scale_idx, int64_t n_rows,
                                                          int n_cols, T *__restrict__ dst) {
-  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t i = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) * 4;   // four consecutive columns
   if (i >= n_rows * n_cols) return;
   const int64_t r = i / n_cols, c = i % n_cols;
   const int64_t rs = src_idx ? src_idx[r] : r, rg = scale_idx ? scale_idx[r] : r;
-  dst[i] = from_f32<T>(to_f32(src[rs * n_cols + c]) * scale[rg]);
+  const float g = scale[rg];
+  float v[4];
+  bwd_load4(src + rs * n_cols + c, v);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) v[q] *= g;
+  bwd_store4(dst + i, v);
 }
 
 // the same contraction on the plain ALUs (fp32, or bf16 shapes the MFMA kernel does not take): 64 x 64 tiles
@@ -928,7 +973,7 @@ hipError_t launch_router_backward(int dtype, const float *logits, const int32_t 
 
 hipError_t launch_dx_finish(int dtype, const void *dx_in, const float *d_logits, const void *w_router, int64_t n_tok,
                             int d_model, int n_experts, void *d_x, hipStream_t s) {
-  const dim3 grid = grid1d(n_tok * d_model, 256);
+  const dim3 grid = grid1d(n_tok * d_model / 4, 256);      // d_model is a multiple of 8
   if (dtype == ROM_DTYPE_BF16)
     hipLaunchKernelGGL((dx_finish_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(dx_in), d_logits,
                        static_cast<const bf16_t *>(w_router), n_tok, d_model, n_experts, static_cast<bf16_t *>(d_x));
@@ -961,14 +1006,16 @@ hipError_t launch_conv_backward(int dtype, const void *xz, int64_t ld_xz, const 
 }
 
 hipError_t launch_transpose(int dtype, const void *src, void *dst, int n_mats, int rows, int cols, hipStream_t s) {
-  const dim3 grid(static_cast<unsigned>(ceil_div(cols, 32)), static_cast<unsigned>(ceil_div(rows, 32)),
+  const dim3 grid(static_cast<unsigned>(ceil_div(cols, 64)), static_cast<unsigned>(ceil_div(rows, 64)),
                   static_cast<unsigned>(n_mats));
+  const int vec = rows % 4 == 0 && cols % 4 == 0 && reinterpret_cast<uintptr_t>(src) % 16 == 0 &&
+                  reinterpret_cast<uintptr_t>(dst) % 16 == 0;
   if (dtype == ROM_DTYPE_BF16)
     hipLaunchKernelGGL((transpose_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(src),
-                       static_cast<bf16_t *>(dst), rows, cols);
+                       static_cast<bf16_t *>(dst), rows, cols, vec);
   else
     hipLaunchKernelGGL((transpose_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(src),
-                       static_cast<float *>(dst), rows, cols);
+                       static_cast<float *>(dst), rows, cols, vec);
   return hipGetLastError();
 }
 
@@ -986,7 +1033,8 @@ hipError_t launch_pack_dxdbl(int dtype, const float *d_dt_low, const float *d_bc
 
 hipError_t launch_scale_rows(int dtype, const void *src, const float *scale, const int32_t *src_idx,
                              const int32_t *scale_idx, int64_t n_rows, int n_cols, void *dst, hipStream_t s) {
-  const dim3 grid = grid1d(n_rows * n_cols, 256);
+  if (n_cols % 4 != 0) return hipErrorInvalidValue;       // (d_model is a multiple of 8)
+  const dim3 grid = grid1d(n_rows * n_cols / 4, 256);
   if (dtype == ROM_DTYPE_BF16)
     hipLaunchKernelGGL((scale_rows_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(src), scale,
                        src_idx, scale_idx, n_rows, n_cols, static_cast<bf16_t *>(dst));
