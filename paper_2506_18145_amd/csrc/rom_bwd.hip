@@ -4,6 +4,8 @@
 // Eq. (2), gradient of the gate weights of Eq. (9)/(12), and the gather / transpose kernels that
 // bring activations into the layout the weight-gradient GEMMs contract over.
 // Correct-first: plain ALU kernels, deterministic (fixed summation orders, no atomics).
+#include <atomic>
+#include <mutex>
 #include "rom_internal.h"
 
 namespace rom {
@@ -748,7 +750,7 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const bf16_t *__restric
   const int frag_row = lane & 31, frag_half = lane >> 5;
   // staging: a slab is 64 positions; threads 0..127 bring the A operand, 128..255 the B operand, each an
   // 8-position x 8-column block: (position group pg = 0..7, column piece = 0..15)
-  const bool is_a = tid < 128;
+  const bool is_a = __builtin_amdgcn_readfirstlane(tid < 128 ? 1 : 0) != 0;      // wave-uniform
   const int t2 = tid & 127, pg = t2 & 7, piece = t2 >> 3;       // 16 consecutive lanes park into 64 distinct banks
   const bf16_t *src = is_a ? A : Bm;
   const int32_t *rows = is_a ? rows_a : rows_b;      // position -> row of this operand (NULL: the position itself)
@@ -757,16 +759,23 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const bf16_t *__restric
   const bool col_ok = col < (is_a ? M : N);
   bf16_t(*dst)[kWgPitch] = is_a ? As : Bs;
   for (int64_t p0 = p_lo; p0 < p_hi; p0 += kWgSlab) {
+    // (branch-free, indices first: see the 256 x 256 kernel)
     u32x4_t v[8];
+    int64_t r[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int64_t p = p0 + pg * 8 + i;
-      v[i] = u32x4_t{0u, 0u, 0u, 0u};
-      if (p < p_hi && col_ok) {
-        const int64_t r = rows ? rows[p] : p;
-        v[i] = *reinterpret_cast<const u32x4_t *>(src + r * ld + col);
-      }
+      r[i] = p < p_hi ? p : p_hi - 1;
     }
+    if (rows) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) r[i] = rows[r[i]];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const u32x4_t *>(src + r[i] * ld + (col_ok ? col : 0));
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (p0 + pg * 8 + i >= p_hi || !col_ok) v[i] = u32x4_t{0u, 0u, 0u, 0u};
     __syncthreads();                       // the slab before this one has been multiplied
     wgrad_park8x8(v, dst, piece * 8, pg * 8);
     __syncthreads();
@@ -796,6 +805,139 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const bf16_t *__restric
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int cc = n0 + wn * 64 + j * 32 + q * 8 + frag_half * 4;
+        if (m < M && cc + 3 < N)
+          *reinterpret_cast<float4 *>(Ce + static_cast<int64_t>(m) * N + cc) =
+              make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        else
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (m < M && cc + r < N) Ce[static_cast<int64_t>(m) * N + cc + r] = acc[i][j][4 * q + r];
+      }
+  }
+}
+
+// The same contraction for outputs of at least 256 x 256 per expert (the in and out projections):
+// a 256 x 256 tile on eight waves (4 x 2, 64 x 128 each: 2 x 4 MFMA accumulators, six fragment
+// reads per eight MFMAs instead of four per four, because the fragment reads out of LDS are what
+// bounds the small tile), two LDS buffers so that the next slab is fetched into registers while
+// this one is multiplied and parked into the other buffer afterwards: one barrier per slab.
+constexpr int kWgBig = 256;
+constexpr int kWgBigSmem = 2 * 2 * kWgBig * kWgPitch * 2;      // two buffers x (A, B) x 256 rows x 144 bytes
+__global__ __launch_bounds__(512) void wgrad_bf16_big_kernel(const bf16_t *__restrict__ A, int64_t lda, int M,
+                                                             const bf16_t *__restrict__ Bm, int64_t ldb, int N,
+                                                             const int32_t *__restrict__ rows_a,
+                                                             const int32_t *__restrict__ rows_b,
+                                                             const int32_t *__restrict__ offsets, int64_t n_pos,
+                                                             int n_groups, float *__restrict__ C) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char wg_smem[];
+  typedef bf16_t (*Tile)[kWgPitch];
+  // Workgroup ids go round the eight XCDs; logical tiles (column tile fastest, then row tile, then
+  // expert) are dealt so that an XCD works on a contiguous run of them: the 32 tiles its CUs hold at
+  // a time share their A and B column blocks in that XCD's L2 instead of each fetching its own.
+  const int tn = (N + kWgBig - 1) / kWgBig, tm = (M + kWgBig - 1) / kWgBig;
+  const int per_xcd = gridDim.x / 8;                             // the grid is padded to a multiple of 8
+  const int t = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (t >= tn * tm * n_groups) return;
+  const int e = t / (tn * tm);
+  const int64_t p_lo = offsets ? offsets[e] : 0, p_hi = offsets ? offsets[e + 1] : n_pos;
+  const int m0 = ((t / tn) % tm) * kWgBig, n0 = (t % tn) * kWgBig;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 3, wn = wave >> 2;                       // 4 x 2 waves, 64 x 128 each
+  f32x16_t acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+  const int frag_row = lane & 31, frag_half = lane >> 5;
+  // staging: threads 0..255 bring the A operand, 256..511 the B operand, each an 8-position x 8-column
+  // block of the slab's 64 positions x 256 columns: (position group pg = 0..7, column piece = 0..31)
+  // (wave-uniform, and said so: with a per-lane operand choice the row map's NULL test is a divergent
+  // branch around every index load, each followed by its own wait)
+  const bool is_a = __builtin_amdgcn_readfirstlane(tid < 256 ? 1 : 0) != 0;
+  const int t2 = tid & 255, pg = t2 & 7, piece = t2 >> 3;
+  const bf16_t *src = is_a ? A : Bm;
+  const int32_t *rows = is_a ? rows_a : rows_b;
+  const int64_t ld = is_a ? lda : ldb;
+  const int col = (is_a ? m0 : n0) + piece * 8;
+  const bool col_ok = col < (is_a ? M : N);
+  auto tile_of = [&](int buf, bool a_side) {
+    return reinterpret_cast<Tile>(wg_smem + (static_cast<size_t>(buf) * 2 + (a_side ? 0 : 1)) * kWgBig * kWgPitch * 2);
+  };
+  u32x4_t v[8];
+  // Branch-free: the eight row indices first, then the eight rows (positions past the group's end
+  // re-read its last row, columns past the matrix re-read column 0, and are zeroed afterwards) - with
+  // a branch per row the compiler waits for each index and each row in turn, sixteen dependent
+  // memory round trips per slab.
+  const int col_c = col_ok ? col : 0;
+  // (requesting the row indices a further slab ahead, so that their round trip is hidden too,
+  // measured slower: 0.78 -> 0.94 ms)
+  auto fetch = [&](int64_t p0) __attribute__((always_inline)) {
+    int64_t r[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int64_t p = p0 + pg * 8 + i;
+      r[i] = p < p_hi ? p : p_hi - 1;
+    }
+    if (rows) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) r[i] = rows[r[i]];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const u32x4_t *>(src + r[i] * ld + col_c);
+  };
+  // zeroes what fetch(p0) read past the group's end or past the matrix; called where the rows are
+  // parked, not where they are requested, so that the wait for them comes after the MFMAs
+  auto mask = [&](int64_t p0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (p0 + pg * 8 + i >= p_hi || !col_ok) v[i] = u32x4_t{0u, 0u, 0u, 0u};
+  };
+  if (p_lo < p_hi) {
+    fetch(p_lo);
+    mask(p_lo);
+    wgrad_park8x8(v, tile_of(0, is_a), piece * 8, pg * 8);
+  }
+  __syncthreads();
+  int buf = 0;
+  for (int64_t p0 = p_lo; p0 < p_hi; p0 += kWgSlab, buf ^= 1) {
+    const bool has_next = p0 + kWgSlab < p_hi;
+    if (has_next) fetch(p0 + kWgSlab);                 // in flight while this slab is multiplied
+    const Tile As = tile_of(buf, true), Bs = tile_of(buf, false);
+#pragma unroll
+    for (int kk = 0; kk < kWgSlab / 16; ++kk) {
+      bf16x8_t fa[2], fb[4];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        fa[i] = *reinterpret_cast<const bf16x8_t *>(&As[wm * 64 + i * 32 + frag_row][kk * 16 + frag_half * 8]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        fb[j] = *reinterpret_cast<const bf16x8_t *>(&Bs[wn * 128 + j * 32 + frag_row][kk * 16 + frag_half * 8]);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    // the other buffer was last read in the iteration before this one, which every wave has left
+    if (has_next) {
+      mask(p0 + kWgSlab);
+      wgrad_park8x8(v, tile_of(buf ^ 1, is_a), piece * 8, pg * 8);
+    }
+    __syncthreads();
+  }
+  // the B fragment is the MFMA's row operand: this lane holds, for output row m = frag_row, the
+  // columns 8 q + 4 frag_half + r of each 32-wide tile in accumulator element 4 q + r
+  float *Ce = C + static_cast<int64_t>(e) * M * N;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int m = m0 + wm * 64 + i * 32 + frag_row;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int cc = n0 + wn * 128 + j * 32 + q * 8 + frag_half * 4;
         if (m < M && cc + 3 < N)
           *reinterpret_cast<float4 *>(Ce + static_cast<int64_t>(m) * N + cc) =
               make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
@@ -1049,6 +1191,29 @@ hipError_t launch_wgrad(int dtype, const void *A, int64_t lda, int M, const void
                         int n_groups, int64_t n_pos, float *C, hipStream_t s) {
   const bool mfma = dtype == ROM_DTYPE_BF16 && M % 8 == 0 && N % 8 == 0 && lda % 8 == 0 && ldb % 8 == 0 &&
                     reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(Bm) % 16 == 0;
+  if (mfma && !row_scale && M >= kWgBig && N >= kWgBig) {
+    // more than 64 KiB of dynamic LDS: a function attribute, set once per device
+    static std::mutex mu;
+    static std::atomic<bool> done[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!done[dev].load(std::memory_order_acquire)) {
+      std::lock_guard<std::mutex> lock(mu);
+      if (!done[dev].load(std::memory_order_relaxed)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_bf16_big_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kWgBigSmem);
+        if (e != hipSuccess) return e;
+        done[dev].store(true, std::memory_order_release);
+      }
+    }
+    const int64_t tiles = ceil_div(N, kWgBig) * ceil_div(M, kWgBig) * n_groups;
+    const dim3 grid(static_cast<unsigned>(ceil_div(tiles, 8) * 8));
+    hipLaunchKernelGGL(wgrad_bf16_big_kernel, grid, dim3(512), kWgBigSmem, s, static_cast<const bf16_t *>(A), lda, M,
+                       static_cast<const bf16_t *>(Bm), ldb, N, rows_a, rows_b, offsets, n_pos, n_groups, C);
+    return hipGetLastError();
+  }
   if (mfma && !row_scale) {
     const dim3 grid(static_cast<unsigned>(ceil_div(N, kWgTile)), static_cast<unsigned>(ceil_div(M, kWgTile)),
                     static_cast<unsigned>(n_groups));
