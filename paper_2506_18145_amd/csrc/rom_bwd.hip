@@ -343,11 +343,22 @@ __global__ __launch_bounds__(256) void scan_bwd_kernel(
       }
 #pragma unroll
       for (int half = 1; half >= 0; --half) {
+        // the eight steps' LDS operands in one batch: one wait instead of one per step behind the
+        // step's own LDS writes
+        float us8[kBwdHalf], cn8[kBwdHalf], dy8[kBwdHalf], dzf8[kBwdHalf];
+#pragma unroll
+        for (int jj = 0; jj < kBwdHalf; ++jj) {
+          const int s2 = grp * kBwdGroup + half * kBwdHalf + jj;
+          us8[jj] = sm.u[s2][cl];
+          cn8[jj] = sm.bc[s2][16 + n];
+          dy8[jj] = sm.dy[s2][cl];
+          dzf8[jj] = sm.dzf[s2][cl];
+        }
 #pragma unroll
         for (int jj = kBwdHalf - 1; jj >= 0; --jj) {
           const int j = half * kBwdHalf + jj;
           const int s2 = grp * kBwdGroup + j;
-          const float us = sm.u[s2][cl], cn = sm.bc[s2][16 + n], dy = sm.dy[s2][cl];
+          const float us = us8[jj], cn = cn8[jj], dy = dy8[jj];
           const float y = row_sum16(cn * hs[j + 1]) + d_skip * us;
           dh = fmaf(cn, dy, dh);                                // y_t = C_t . h_t
           const float darg = dh * hs[j] * da[j];                // d / d (dt_t * A)
@@ -363,7 +374,7 @@ __global__ __launch_bounds__(256) void scan_bwd_kernel(
           const float dpre = ddt * (1.0f - fast_exp2(-1.44269504088896341f * dts[j]));
           sm.o_pre[s2][cl] = dpre;
           sm.o_u[s2][cl] = du;
-          sm.o_z[s2][cl] = sm.dzf[s2][cl] * y;
+          sm.o_z[s2][cl] = dzf8[jj] * y;
           acc_bias += dpre;
           acc_d = fmaf(dy, us, acc_d);
         }
