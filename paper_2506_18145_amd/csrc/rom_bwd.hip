@@ -24,6 +24,60 @@ __device__ __forceinline__ float row_sum16(float v) {
   v = dpp<0xB1>(v) + v;       // quad_perm [1,0,3,2]
   return v;
 }
+
+// Sixteen values per lane, each to be summed over the 16 lanes of a row: a butterfly that halves
+// the number of live values at every stage (the lanes with bit 3 / 2 / 1 / 0 of n set keep the upper
+// half) leaves the row total of p[n] in lane n - 30 DPP adds and 15 selects instead of 64 adds.
+__device__ __forceinline__ float transpose_sum16(const float *p, int n) {
+#pragma clang fp contract(off)
+  float a[8], b[4], c[2];
+  const bool hi8 = (n & 8) != 0, hi4 = (n & 4) != 0, hi2 = (n & 2) != 0, hi1 = (n & 1) != 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float lo = dpp<0x140>(p[j]) + p[j];
+    const float hi = dpp<0x140>(p[j + 8]) + p[j + 8];
+    a[j] = hi8 ? hi : lo;
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float lo = dpp<0x141>(a[j]) + a[j];
+    const float hi = dpp<0x141>(a[j + 4]) + a[j + 4];
+    b[j] = hi4 ? hi : lo;
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const float lo = dpp<0x1B>(b[j]) + b[j];
+    const float hi = dpp<0x1B>(b[j + 2]) + b[j + 2];
+    c[j] = hi2 ? hi : lo;
+  }
+  const float lo = dpp<0xB1>(c[0]) + c[0];
+  const float hi = dpp<0xB1>(c[1]) + c[1];
+  return hi1 ? hi : lo;
+}
+// the same for eight values: lane n ends up with the row total of p[n & 7]
+__device__ __forceinline__ float transpose_sum8(const float *p, int n) {
+#pragma clang fp contract(off)
+  float a[8], b[4], c[2];
+  const bool hi4 = (n & 4) != 0, hi2 = (n & 2) != 0, hi1 = (n & 1) != 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) a[j] = dpp<0x140>(p[j]) + p[j];       // pairs (i, 15 - i): both halves of the row alike
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float lo = dpp<0x141>(a[j]) + a[j];
+    const float hi = dpp<0x141>(a[j + 4]) + a[j + 4];
+    b[j] = hi4 ? hi : lo;
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const float lo = dpp<0x1B>(b[j]) + b[j];
+    const float hi = dpp<0x1B>(b[j + 2]) + b[j + 2];
+    c[j] = hi2 ? hi : lo;
+  }
+  const float lo = dpp<0xB1>(c[0]) + c[0];
+  const float hi = dpp<0xB1>(c[1]) + c[1];
+  return hi1 ? hi : lo;
+}
+
 __device__ __forceinline__ float sigmoid_f32(float v) { return fast_rcp(1.0f + fast_exp2(-1.44269504088896341f * v)); }
 
 inline dim3 grid1d(int64_t work, int block) { return dim3(static_cast<unsigned>(ceil_div(work, block))); }
@@ -100,7 +154,12 @@ struct BwdSmem {
   float bc[kBwdTile][33];                    // B_0..15, C_0..15 of every step
   float o_pre[kBwdTile][kBwdPitch], o_u[kBwdTile][kBwdPitch], o_z[kBwdTile][kBwdPitch];   // outputs of the tile
   float o_bc[kBwdTile][33];                  // this block's share of d_B, d_C of the tile
-  float part_b[kBwdHalf][kBwdCh][17], part_c[kBwdHalf][kBwdCh][17];   // [step in half group][channel][state] terms of d_B, d_C
+  // [step in half group][channel][state] terms of d_B, d_C.  The channel sums read both arrays with
+  // one instruction (32 lanes per step: 16 states of each); the pad puts part_c half the banks away
+  // from part_b, so that the 64 lanes of a wave (two steps) touch 64 different banks.
+  float part_b[kBwdHalf][kBwdCh][17];
+  float bank_pad[32];
+  float part_c[kBwdHalf][kBwdCh][17];
 };
 
 // What the carry kernel needs of a tile: a third of the LDS, so that seven of its blocks fit a CU
@@ -270,7 +329,7 @@ __global__ __launch_bounds__(256) void scan_bwd_kernel(
   const float d_skip = D[ch];
   float *ck = ckpt + unit * (chunk_len / kBwdGroup) * 256;
   const int64_t n_tok = n_seq * L;
-  float acc_a = 0.0f, acc_d = 0.0f, acc_bias = 0.0f;       // d_A (this lane's state); d_D, d_dt_bias (alike in the 16 lanes of a channel)
+  float acc_a = 0.0f, acc_d = 0.0f, acc_bias = 0.0f;       // d_A (this lane's state); d_D, d_dt_bias (the steps this lane finishes)
 
   const T *u_b = u + b * L * d_inner + c0;
   const T *dt_b = dt + b * L * d_inner + c0;
@@ -345,38 +404,49 @@ __global__ __launch_bounds__(256) void scan_bwd_kernel(
       for (int half = 1; half >= 0; --half) {
         // the eight steps' LDS operands in one batch: one wait instead of one per step behind the
         // step's own LDS writes
-        float us8[kBwdHalf], cn8[kBwdHalf], dy8[kBwdHalf], dzf8[kBwdHalf];
+        float us8[kBwdHalf], cn8[kBwdHalf], dy8[kBwdHalf];
 #pragma unroll
         for (int jj = 0; jj < kBwdHalf; ++jj) {
           const int s2 = grp * kBwdGroup + half * kBwdHalf + jj;
           us8[jj] = sm.u[s2][cl];
           cn8[jj] = sm.bc[s2][16 + n];
           dy8[jj] = sm.dy[s2][cl];
-          dzf8[jj] = sm.dzf[s2][cl];
         }
+        // per (step, state) part: the adjoint recurrence and the terms whose sums over the 16 states
+        // the step's outputs need: y (p16[jj]), the input term (p16[8 + jj]), d dt (q8[jj])
+        float p16[2 * kBwdHalf], q8[kBwdHalf];
 #pragma unroll
         for (int jj = kBwdHalf - 1; jj >= 0; --jj) {
           const int j = half * kBwdHalf + jj;
-          const int s2 = grp * kBwdGroup + j;
-          const float us = us8[jj], cn = cn8[jj], dy = dy8[jj];
-          const float y = row_sum16(cn * hs[j + 1]) + d_skip * us;
-          dh = fmaf(cn, dy, dh);                                // y_t = C_t . h_t
+          dh = fmaf(cn8[jj], dy8[jj], dh);                      // y_t = C_t . h_t
+          p16[jj] = cn8[jj] * hs[j + 1];
           const float darg = dh * hs[j] * da[j];                // d / d (dt_t * A)
           const float inj = dh * bn[j];                         // input term dt * B * u
-          const float ddt = row_sum16(fmaf(darg, a_nat, inj * us));
-          const float du = fmaf(row_sum16(inj), dts[j], d_skip * dy);
+          p16[kBwdHalf + jj] = inj;
+          q8[jj] = fmaf(darg, a_nat, inj * us8[jj]);
           acc_a = fmaf(darg, dts[j], acc_a);
           sm.part_b[jj][cl][n] = dh * dtu[j];
-          sm.part_c[jj][cl][n] = dy * hs[j + 1];
+          sm.part_c[jj][cl][n] = dy8[jj] * hs[j + 1];
           dh *= da[j];
-          // (all 16 lanes of the channel hold the same sums and write the same value)
-          // dt = softplus(pre): d pre = d dt * sigmoid(pre) = d dt * (1 - exp(-dt))
-          const float dpre = ddt * (1.0f - fast_exp2(-1.44269504088896341f * dts[j]));
-          sm.o_pre[s2][cl] = dpre;
-          sm.o_u[s2][cl] = du;
-          sm.o_z[s2][cl] = dzf8[jj] * y;
-          acc_bias += dpre;
-          acc_d = fmaf(dy, us, acc_d);
+        }
+        // sums over the states, transposed: lane n < 8 holds C.h of step n, lane n >= 8 the input-term
+        // sum of step n - 8, every lane the d dt sum of step n & 7
+        const float yi = transpose_sum16(p16, n);
+        const float ddt = transpose_sum8(q8, n);
+        // per (step, channel) part, once per step instead of once per lane: lane n works on step n & 7
+        {
+          const int s2 = grp * kBwdGroup + half * kBwdHalf + (n & 7);
+          const float dt_k = sm.dt[s2][cl], u_k = sm.u[s2][cl], dy_k = sm.dy[s2][cl];
+          if (n < 8) {
+            sm.o_z[s2][cl] = sm.dzf[s2][cl] * fmaf(d_skip, u_k, yi);
+            // dt = softplus(pre): d pre = d dt * sigmoid(pre) = d dt * (1 - exp(-dt))
+            const float dpre = ddt * (1.0f - fast_exp2(-1.44269504088896341f * dt_k));
+            sm.o_pre[s2][cl] = dpre;
+            acc_bias += dpre;
+            acc_d = fmaf(dy_k, u_k, acc_d);
+          } else {
+            sm.o_u[s2][cl] = fmaf(yi, dt_k, d_skip * dy_k);
+          }
         }
         lds_barrier();
         // d_B, d_C of these eight steps: sum over the block's channels in channel order
@@ -417,6 +487,9 @@ __global__ __launch_bounds__(256) void scan_bwd_kernel(
     }
   }
   part_a[unit * 256 + tid] = acc_a * a_nat;                            // d A_log = d A * A
+  // (lanes 0..7 of a channel each hold the sums over the steps they worked on, lanes 8..15 zero)
+  acc_d = row_sum16(acc_d);
+  acc_bias = row_sum16(acc_bias);
   if (n == 0) {
     part_d[unit * kBwdCh + cl] = acc_d;
     part_bias[unit * kBwdCh + cl] = acc_bias;

@@ -60,28 +60,14 @@ __host__ __device__ __forceinline__ int patch_n_for(int n_tiles) {
   return pn;
 }
 
-// A group whose last row tile holds at most kTailRows rows can hand that tile to narrow column
-// units (kTailBN columns each, all of K) that are dispatched ahead of the full tiles: a 256-row
-// tile with a few valid rows costs a CU a whole walk over K, and with one tile resident per CU a
-// handful of such tiles makes a round of their own at the end of the launch.
-// Built, parity-tested and switched off (kUseTailUnits): every unit re-loads the tail's activation
-// rows, and a DMA instruction whose lanes all point into one line still costs its 64 lanes, so
-// the units of a tail cost more CU time than the tail tile did.  Measured at d_model 2048, 16K
-// tokens, 8 experts: in projection 0.56 -> 0.63 ms, out projection 0.315 -> 0.319 ms.
-constexpr int kTailRows = 128, kTailBN = 64;
-__device__ __forceinline__ bool tail_is_narrow(const GemmArgs &a, int rows, int BM) {
-  const int v = rows % BM;
-  return a.tail_units > 0 && v > 0 && v <= kTailRows;
-}
-
 __device__ __forceinline__ TileCoord locate_tile(const GemmArgs &a, int BM, int BN) {
   TileCoord tc;
   tc.valid = false;
   const int n_tiles = (a.N + BN - 1) / BN;
   const int pn = patch_n_for(n_tiles), pm = kPatchTiles / pn;
   const int patches_n = (n_tiles + pn - 1) / pn;
-  const int G = gridDim.x - a.tail_units;               // (tail_units is a multiple of 8: block id mod 8 = XCD either way)
-  const int bid = blockIdx.x - a.tail_units;
+  const int G = gridDim.x;
+  const int bid = blockIdx.x;
   int t = bid;
   if (kXcdRemap && !a.no_xcd_remap && G % 8 == 0) t = (bid % 8) * (G / 8) + bid / 8;
   const int patch = t / kPatchTiles, in_patch = t % kPatchTiles;
@@ -98,7 +84,7 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmArgs &a, int BM, int 
     int rem = mt;
     for (int e = 0; e < a.n_groups; ++e) {
       const int lo = a.offsets[e], hi = a.offsets[e + 1];
-      const int tiles = tail_is_narrow(a, hi - lo, BM) ? (hi - lo) / BM : (hi - lo + BM - 1) / BM;
+      const int tiles = (hi - lo + BM - 1) / BM;
       if (rem < tiles) {
         tc.group = e;
         tc.row0 = lo + static_cast<int64_t>(rem) * BM;
@@ -110,23 +96,6 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmArgs &a, int BM, int 
     }
   }
   if (tc.valid && tc.row_end > tc.row0 + BM) tc.row_end = tc.row0 + BM;
-  return tc;
-}
-
-// workgroup id -> narrow unit (group, column slice) over the group's short last row tile
-__device__ __forceinline__ TileCoord locate_tail_unit(const GemmArgs &a, int BM) {
-  TileCoord tc;
-  tc.valid = false;
-  const int units_per_group = (a.N + kTailBN - 1) / kTailBN;
-  const int e = blockIdx.x / units_per_group, j = blockIdx.x % units_per_group;
-  if (e >= a.n_groups) return tc;
-  const int lo = a.offsets[e], hi = a.offsets[e + 1];
-  if (!tail_is_narrow(a, hi - lo, BM)) return tc;
-  tc.group = e;
-  tc.row0 = lo + static_cast<int64_t>((hi - lo) / BM) * BM;
-  tc.row_end = hi;
-  tc.n0 = j * kTailBN;
-  tc.valid = true;
   return tc;
 }
 
@@ -721,23 +690,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_dma_kernel(const GemmAr
   dma_tile<BN, WM, WN, EPI>(a, tc, smem);
 }
 
-// The 256x256 tiles of a grouped launch behind the narrow units over the groups' short last row
-// tiles (see kTailRows): workgroups [0, tail_units) are units (group, 64-column slice), eight
-// waves stacked over the 256 rows; the rest are the full tiles.
-template <int EPI>
-__global__ __launch_bounds__(512) void gemm_bf16_dma_tails_kernel(const GemmArgs a) {
-  extern __shared__ __attribute__((aligned(16))) uint4 smem[];
-  if (static_cast<int>(blockIdx.x) < a.tail_units) {
-    const TileCoord tc = locate_tail_unit(a, 256);
-    if (!tc.valid) return;
-    dma_tile<kTailBN, 8, 1, EPI>(a, tc, smem);
-  } else {
-    const TileCoord tc = locate_tile(a, 256, 256);
-    if (!tc.valid) return;
-    dma_tile<256, kBigWM, kBigWN, EPI>(a, tc, smem);
-  }
-}
-
 // ------------------------------------------------------------------ bf16 MFMA kernel, short inner dimension
 // For K <= 128 (the dt projection: K = dt_rank) there is no K loop to pipeline: a tile of the
 // general kernel is one load, a few MFMAs and a long epilogue in sequence, and the epilogue
@@ -991,20 +943,6 @@ hipError_t launch_dma(const GemmArgs &a, hipStream_t s) {
                      dim3(WM * WN * 64), kSmem, s, a);
   return hipGetLastError();
 }
-template <int EPI>
-hipError_t launch_dma_tails(const GemmArgs &args, hipStream_t s) {
-  constexpr int kSmem = kDmaSlots * 256 * kDmaRC * 16;     // 160 KiB
-  static LdsAttrOnce attr;
-  const hipError_t e = attr.ensure(reinterpret_cast<const void *>(&gemm_bf16_dma_tails_kernel<EPI>), kSmem);
-  if (e != hipSuccess) return e;
-  GemmArgs a = args;
-  const int units = a.n_groups * static_cast<int>(ceil_div(a.N, kTailBN));
-  a.tail_units = (units + 7) / 8 * 8;
-  hipLaunchKernelGGL((gemm_bf16_dma_tails_kernel<EPI>), dim3(a.tail_units + grid_tiles(a, 256, 256)), dim3(512), kSmem, s, a);
-  return hipGetLastError();
-}
-constexpr bool kUseTailUnits = false;   // measured slower, see the comment at kTailRows
-
 // the DMA kernel addresses both operands with unsigned 32-bit byte offsets and walks whole 64-wide slabs
 inline bool dma_ok(const GemmArgs &a) {
   return kUseDma && a.K % kDmaBK == 0 && a.k_per_split % kDmaBK == 0 && a.lda >= a.K &&
@@ -1017,9 +955,6 @@ hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
   // a short inner dimension makes the launch epilogue-bound: smaller tiles put several
   // workgroups on a CU so that loads, MFMAs and stores of different tiles overlap
   if (rows_per_group >= 1024 && a.N >= 256 && a.K > 256) {
-    if (kUseTailUnits && dma_ok(a) && a.k_splits == 1 && a.offsets && a.N % kTailBN == 0 &&
-        EPI != kEpiPlainF32)
-      return launch_dma_tails<EPI>(a, s);
     if (dma_ok(a) && a.k_splits == 1) return launch_dma<256, kBigWM, kBigWN, EPI>(a, s);
     return launch_mfma<256, 256, 4, 2, EPI>(a, s);
   }

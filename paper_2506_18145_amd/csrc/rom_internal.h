@@ -93,8 +93,6 @@ struct GemmArgs {
                              // epilogue only) to C + s * c_split_stride; the consumer adds the slices up
   int64_t c_split_stride;    // elements between the outputs of consecutive slices
   int k_per_split;           // filled in by launch_grouped_gemm
-  int tail_units;            // filled in by the launcher: the first tail_units workgroups of the grid are narrow
-                             // column units over the short last row tile of a group (0: every tile is a full tile)
 };
 hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s);
 bool grouped_gemm_on_mfma(const GemmArgs &a);
