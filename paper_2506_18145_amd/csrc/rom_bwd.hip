@@ -164,7 +164,7 @@ struct BwdSmem {
 
 // What the carry kernel needs of a tile: a third of the LDS, so that seven of its blocks fit a CU
 struct BwdCarrySmem {
-  float dt[kBwdTile][kBwdPitch], u[kBwdTile][kBwdPitch], dy[kBwdTile][kBwdPitch];
+  float dt[kBwdTile][kBwdPitch], u[kBwdTile][kBwdPitch], dy[kBwdTile][kBwdPitch];     // (u: dt * u)
   float bc[kBwdTile][33];
 };
 
@@ -227,13 +227,15 @@ __device__ __forceinline__ void bwd_fetch_tile(BwdTileRegs &r, const T *u_b, con
   }
 }
 
+// kWithDz: the full set of factors the main kernel's second pass needs; without it (the carry kernel)
+// the u slot holds dt * u, the only form that kernel uses u in
 template <typename Smem, bool kWithDz>
 __device__ __forceinline__ void bwd_park_tile(Smem &sm, const BwdTileRegs &r, int tid, bool full) {
   const int row = tid >> 2, c = (tid & 3) * 4;
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     sm.dt[row][c + q] = r.dt[q];
-    sm.u[row][c + q] = r.u[q];
+    sm.u[row][c + q] = kWithDz ? r.u[q] : r.dt[q] * r.u[q];
     if (full) {
       const float zs = r.z[q], dgs = r.dg[q];
       const float sig = sigmoid_f32(zs);
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(256) void scan_bwd_carry_kernel(
     for (int s2 = 0; s2 < kBwdTile; ++s2) {
       const float dts = sm.dt[s2][cl];
       sum_dt += dts;
-      h = fmaf(fast_exp2(dts * a2), h, dts * sm.u[s2][cl] * sm.bc[s2][n]);
+      h = fmaf(fast_exp2(dts * a2), h, sm.u[s2][cl] * sm.bc[s2][n]);      // (u slot: dt * u)
     }
   }
   float gq = 0.0f;
