@@ -5,8 +5,13 @@ model (d_model 2048, 8 experts top-1, L = 16384).  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--no-cpu-baseline]
 
-Inputs and weights are resident in HBM before the timed region starts.  Per-stage durations come
-from HIP events the library records on the launch stream inside the timed region.
+Inputs and weights are resident in HBM before the timed region starts.  The timed calls carry HIP
+events around the dominant kernel (the in projection) only; the per-stage breakdown comes from a
+second pass with an event at every stage boundary.  Beside the headline: HBM traffic of the
+dominant kernel from two rocprofv3 counter runs of this script, forward timings of the two other
+layer configurations, the load-balance statistics, the shared x/dt variant, forward + backward of
+the layer, a 48-block stack, the FFN-MoE layer, the recurrent step and the CPU oracle's rate
+(--help lists the switches that skip them; --probe prints issue-rate measurements instead).
 """
 import argparse
 import json
