@@ -378,14 +378,26 @@ def backward_rate(cfg, steps, warmup):
         evs[i + 1].record()
     torch.cuda.synchronize()
     ms = _median([evs[i].elapsed_time(evs[i + 1]) for i in range(steps)])
+    # a training step: the caller's own forward pass on the backward workspace, then the backward
+    # pass on the activations it left (rom_layer_backward_saved: no recomputation)
+    torch.cuda.synchronize()
+    evs[0].record()
+    for i in range(steps):
+        layer.forward_for_backward(x)
+        d_x, grads = layer.backward(x, d_out, saved=True)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    ms_step = _median([evs[i].elapsed_time(evs[i + 1]) for i in range(steps)])
     n_tok = cfg.batch * cfg.seq_len
     S = n_tok * cfg.top_k
     Sx = S if cfg.routed_xdt else n_tok
     gemm = 2.0 * S * cfg.d_model * 2 * cfg.d_inner + 2.0 * Sx * cfg.d_inner * (cfg.dt_rank + 2 * cfg.d_state) \
         + 2.0 * Sx * cfg.dt_rank * cfg.d_inner + 2.0 * S * cfg.d_inner * cfg.d_model
     finite = bool(torch.isfinite(d_x.float()).all().item()) and all(bool(torch.isfinite(v).all().item()) for v in grads.values())
-    return {"workload": f"{cfg.name}: forward recomputation + backward of one layer (top-1), gradients w.r.t. x and all parameters",
+    return {"workload": f"{cfg.name}: rom_layer_backward (forward recomputation + backward of one layer), gradients "
+                        "w.r.t. x and all parameters; training_step = rom_layer_forward + rom_layer_backward_saved",
             "ms_per_call": ms, "tokens_per_s": n_tok / (ms * 1e-3),
+            "ms_per_training_step": ms_step, "training_tokens_per_s": n_tok / (ms_step * 1e-3),
             "gemm_tflops_forward_plus_backward": 3.0 * gemm / (ms * 1e-3) / 1e12, "gradients_finite": finite}
 
 

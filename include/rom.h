@@ -233,6 +233,16 @@ ROM_API int rom_layer_backward(const rom_dims *dims, const rom_weights *w, const
                        const void *d_out, void *d_x, const rom_grads *grads, void *ws, size_t ws_bytes,
                        void *hip_stream);
 
+/* The same without the forward recomputation, for a training step that has just run the forward pass
+ * itself: the caller's rom_layer_forward(dims, w, x, B, L, NULL, NULL, out, NULL, NULL, ws, ws_bytes,
+ * stream) - zero initial states, the SAME ws of rom_backward_workspace_bytes(dims, B, L) bytes (a
+ * workspace of that size is also a valid forward workspace), the same x and weights, nothing else
+ * writing to ws in between - leaves the activations where this call reads them.  Identical results to
+ * rom_layer_backward, bit for bit; everything else as documented there. */
+ROM_API int rom_layer_backward_saved(const rom_dims *dims, const rom_weights *w, const void *x, int64_t B, int64_t L,
+                             const void *d_out, void *d_x, const rom_grads *grads, void *ws, size_t ws_bytes,
+                             void *hip_stream);
+
 /* ---- Pre-norm residual block (appendix, architectures overview: every layer sits behind a
  * pre-norm and a skip connection):   out = x + RoM(RMSNorm(x)),
  *   RMSNorm(x)[n, :] = x[n, :] / sqrt(mean_d(x[n, d]^2) + eps) * norm_weight[:].

@@ -82,6 +82,8 @@ def load_library() -> ctypes.CDLL:
     lib.rom_layer_backward.restype = ctypes.c_int
     lib.rom_layer_backward.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64, I64, P, P,
                                        ctypes.POINTER(_RomGrads), P, SZ, P]
+    lib.rom_layer_backward_saved.restype = ctypes.c_int
+    lib.rom_layer_backward_saved.argtypes = lib.rom_layer_backward.argtypes
     lib.rom_step_static.restype = ctypes.c_int
     lib.rom_step_static.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64, P, P, P, P]
     F32 = ctypes.c_float
@@ -214,15 +216,17 @@ def rom_backward_workspace_bytes(dims: RomDims, B: int, L: int) -> int:
     return int(load_library().rom_backward_workspace_bytes(ctypes.byref(dims), B, L))
 
 
-def rom_layer_backward(dims, weights, x, B, L, d_out, d_x, grads, ws):
-    """grads: mapping d_<parameter> -> f32 tensor (d_b_router / d_conv_b may be missing or None)."""
+def rom_layer_backward(dims, weights, x, B, L, d_out, d_x, grads, ws, saved=False):
+    """grads: mapping d_<parameter> -> f32 tensor (d_b_router / d_conv_b may be missing or None).
+    saved: rom_layer_backward_saved (ws holds the activations of the caller's own forward call)."""
     gs = _RomGrads()
     for name, _ in _RomGrads._fields_:
         setattr(gs, name, _ptr(grads.get(name)))
-    code = load_library().rom_layer_backward(
-        ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(x), B, L, _ptr(d_out), _ptr(d_x),
-        ctypes.byref(gs), _ptr(ws), _nbytes(ws), _stream())
-    _check(code, "rom_layer_backward")
+    lib = load_library()
+    fn = lib.rom_layer_backward_saved if saved else lib.rom_layer_backward
+    code = fn(ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(x), B, L, _ptr(d_out), _ptr(d_x),
+              ctypes.byref(gs), _ptr(ws), _nbytes(ws), _stream())
+    _check(code, "rom_layer_backward_saved" if saved else "rom_layer_backward")
 
 
 def _nbytes(t) -> int:
@@ -488,21 +492,34 @@ class RomLayer:
         rom_step(self.dims, self.weights, x, B, conv_state, ssm_state, out, self.workspace(max(B, 1), 1))
         return out
 
-    def backward(self, x: torch.Tensor, d_out: torch.Tensor):
-        """(d_x, {d_<parameter>: f32 tensor}) for the layer on input x and upstream gradient d_out."""
-        B, L, _ = x.shape
+    def _backward_workspace(self, B: int, L: int) -> torch.Tensor:
         need = rom_backward_workspace_bytes(self.dims, max(B, 1), max(L, 1))
         if need == 0:
             raise RomError("rom_backward_workspace_bytes returned 0: unsupported dims")
         if self._bwd_ws is None or self._bwd_ws.numel() < need:
             self._bwd_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._bwd_ws
+
+    def forward_for_backward(self, x: torch.Tensor) -> torch.Tensor:
+        """rom_layer_forward into the backward workspace (zero initial states): the out of a training
+        step whose backward(x, d_out, saved=True) then skips the forward recomputation."""
+        B, L, _ = x.shape
+        out = torch.empty_like(x)
+        rom_layer_forward(self.dims, self.weights, x, B, L, None, None, out, None, None, self._backward_workspace(B, L))
+        return out
+
+    def backward(self, x: torch.Tensor, d_out: torch.Tensor, saved: bool = False):
+        """(d_x, {d_<parameter>: f32 tensor}) for the layer on input x and upstream gradient d_out.
+        saved: the activations are those forward_for_backward(x) has just left (rom_layer_backward_saved)."""
+        B, L, _ = x.shape
+        self._backward_workspace(B, L)
         d_x = torch.empty_like(x)
         grads = {}
         for name, _ in _RomGrads._fields_:
             wt = self.weights.get(name[2:])
             if wt is not None:
                 grads[name] = torch.empty(wt.shape, dtype=torch.float32, device=self.device)
-        rom_layer_backward(self.dims, self.weights, x, B, L, d_out, d_x, grads, self._bwd_ws)
+        rom_layer_backward(self.dims, self.weights, x, B, L, d_out, d_x, grads, self._bwd_ws, saved=saved)
         return d_x, grads
 
 

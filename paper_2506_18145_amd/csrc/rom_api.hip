@@ -857,8 +857,25 @@ size_t rom_backward_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L) 
   return make_bwd_plan(dims, B > 0 ? B : 1, L > 0 ? L : 1).total;
 }
 
+namespace {
+int backward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t B, int64_t L, const void *d_out,
+                  void *d_x, const rom_grads *gr, void *ws, size_t ws_bytes, void *hip_stream, bool recompute);
+}
+
 int rom_layer_backward(const rom_dims *d, const rom_weights *w, const void *x, int64_t B, int64_t L, const void *d_out,
                        void *d_x, const rom_grads *gr, void *ws, size_t ws_bytes, void *hip_stream) {
+  return backward_impl(d, w, x, B, L, d_out, d_x, gr, ws, ws_bytes, hip_stream, true);
+}
+
+int rom_layer_backward_saved(const rom_dims *d, const rom_weights *w, const void *x, int64_t B, int64_t L,
+                             const void *d_out, void *d_x, const rom_grads *gr, void *ws, size_t ws_bytes,
+                             void *hip_stream) {
+  return backward_impl(d, w, x, B, L, d_out, d_x, gr, ws, ws_bytes, hip_stream, false);
+}
+
+namespace {
+int backward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t B, int64_t L, const void *d_out,
+                  void *d_x, const rom_grads *gr, void *ws, size_t ws_bytes, void *hip_stream, bool recompute) {
   int rc = check_dims(d);
   if (rc != ROM_OK) return rc;
   rc = check_weights(d, w);
@@ -885,9 +902,12 @@ int rom_layer_backward(const rom_dims *d, const rom_weights *w, const void *x, i
   const bool routed_xdt = Ex > 1, multi = K > 1;
   const int64_t S = N * K;
 
-  // activations: the forward pass into the front part of the workspace
-  rc = forward_impl(d, w, x, B, L, nullptr, nullptr, at(bp.fwd_out), nullptr, nullptr, ws, p.total, s);
-  if (rc != ROM_OK) return rc;
+  // activations: the forward pass into the front part of the workspace, unless the caller's own
+  // rom_layer_forward call on this workspace has just left them there
+  if (recompute) {
+    rc = forward_impl(d, w, x, B, L, nullptr, nullptr, at(bp.fwd_out), nullptr, nullptr, ws, p.total, s);
+    if (rc != ROM_OK) return rc;
+  }
   const int32_t *offsets = reinterpret_cast<const int32_t *>(at(p.offsets));
   const int32_t *tok_of_pos = reinterpret_cast<const int32_t *>(at(p.tok_of_pos));
   const int32_t *perm = reinterpret_cast<const int32_t *>(at(p.perm));
@@ -1001,6 +1021,7 @@ int rom_layer_backward(const rom_dims *d, const rom_weights *w, const void *x, i
   ROM_TRY(launch_dx_finish(d->dtype, at(bp.dx_in), d_logits, w->w_router, N, Dm, E, d_x, s));
   return ROM_OK;
 }
+}  // namespace
 
 const char *rom_strerror(int code) {
   switch (code) {

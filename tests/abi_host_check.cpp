@@ -115,6 +115,8 @@ int main() {
     std::memset(&g, 0, sizeof(g));
     CHECK(rom_layer_backward(&d, &w, addr, 1, 8, addr, addr + 4096, &g, addr, 4096, nullptr) == ROM_E_INVAL);   // NULL gradient pointers
     CHECK(rom_layer_backward(&d, &w, addr, 1, 8, addr, addr + 4096, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_layer_backward_saved(&d, &w, addr, 1, 8, addr, addr + 4096, &g, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_layer_backward_saved(&d, &w, addr, 0, 8, addr, addr + 4096, &g, addr, 4096, nullptr) == ROM_OK);
     // workspace too small
     CHECK(rom_layer_forward(&d, &w, addr, 1, 8, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 16, nullptr) == ROM_E_WORKSPACE);
     // sizes beyond the supported range

@@ -104,6 +104,29 @@ def test_backward_medium(kw):
     run_backward(small_cfg(**kw))
 
 
+@pytest.mark.parametrize("kw", [dict(), dict(top_k=2, gate_mode=1), dict(dtype="fp32", routed_xdt=False),
+                                dict(batch=1, seq_len=3000, d_model=512, d_inner=1024, dt_rank=64, top_k=2, gate_mode=1,
+                                     n_experts=6, cfg_id=163)])
+def test_backward_saved_matches_backward_bit_for_bit(kw):
+    """rom_layer_backward_saved after the caller's own rom_layer_forward on the backward workspace gives
+    the bits of rom_layer_backward (which recomputes the forward pass itself), and the forward's out is
+    that of a plain forward call."""
+    cfg = small_cfg(**kw)
+    w, x = make_weights(cfg), make_input(cfg)
+    layer = RomLayer(cfg, w)
+    xd = layer.to_device(x)
+    dd = layer.to_device(_d_out(cfg, x.shape))
+    d_x, grads = layer.backward(xd, dd)
+    out = layer.forward_for_backward(xd)
+    d_x2, grads2 = layer.backward(xd, dd, saved=True)
+    out_plain = layer.forward(xd)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out_plain)
+    assert torch.equal(d_x, d_x2)
+    for k in grads:
+        assert torch.equal(grads[k], grads2[k]), k
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3"])
 def test_backward_full_size(name):
     run_backward(get_config(name))
