@@ -17,4 +17,9 @@ from .configs import (  # noqa: F401
     make_step_inputs,
     round_to_bf16,
     bf16_bits,
+    Mamba2Config,
+    MAMBA2_CONFIGS,
+    get_mamba2_config,
+    make_mamba2_weights,
+    make_mamba2_input,
 )

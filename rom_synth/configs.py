@@ -189,3 +189,89 @@ def make_step_inputs(cfg: RomConfig, n_steps: Optional[int] = None) -> np.ndarra
     n = cfg.seq_len if n_steps is None else n_steps
     # values are drawn sequentially, so a shorter run is a prefix of a longer one
     return _store(cfg, _normal(cfg, _T_XS, (n, cfg.batch, cfg.d_model), 1.0))
+
+
+# --------------------------------------------------------------------------
+# RoM on a Mamba2 layer (Sec. 5.2, Table 3): shapes of the published Mamba2 layer
+# (expand 2, head dimension 64, state size 128, one B/C group, conv width 4)
+# --------------------------------------------------------------------------
+@dataclass(frozen=True)
+class Mamba2Config:
+    name: str
+    cfg_id: int          # seed base = 1000 * cfg_id + tensor id
+    batch: int
+    seq_len: int
+    d_model: int
+    d_inner: int
+    d_state: int
+    headdim: int
+    n_experts: int
+    top_k: int
+    gate_mode: int
+    dtype: str = "bf16"
+    d_conv: int = 4
+    weight_std: float = 0.02
+    rms_norm_x: bool = False
+    router_bias: Optional[tuple] = None
+
+    @property
+    def n_heads(self) -> int:
+        return self.d_inner // self.headdim
+
+    @property
+    def n_tokens(self) -> int:
+        return self.batch * self.seq_len
+
+    @property
+    def d_in_proj(self) -> int:          # rows of one expert's input projection: z | x | B | C | dt
+        return 2 * self.d_inner + 2 * self.d_state + self.n_heads
+
+    @property
+    def d_conv_ch(self) -> int:          # channels the short conv runs over: x | B | C
+        return self.d_inner + 2 * self.d_state
+
+
+MAMBA2_CONFIGS: Dict[str, Mamba2Config] = {
+    # small: several chunks, a ragged tail, two sequences
+    "m2_small": Mamba2Config("m2_small", 20, 2, 200, 256, 512, 64, 64, 4, 1, 0),
+    # mid: top-2 with renormalised gates, state size 128
+    "m2_mid": Mamba2Config("m2_mid", 21, 2, 1500, 512, 1024, 128, 64, 6, 2, 1),
+    # the headline layer's Mamba2 counterpart: 16K context, d_model 2048, 8 experts top-1
+    "m2_cfg2": Mamba2Config("m2_cfg2", 22, 1, 16384, 2048, 4096, 128, 64, 8, 1, 0,
+                            weight_std=0.02 / float(np.sqrt(2 * 48)), rms_norm_x=True),
+}
+
+
+def get_mamba2_config(name: str, **overrides) -> Mamba2Config:
+    cfg = MAMBA2_CONFIGS[name]
+    return replace(cfg, **overrides) if overrides else cfg
+
+
+def make_mamba2_weights(cfg: Mamba2Config) -> Dict[str, Optional[np.ndarray]]:
+    """w_router [E, d_model], b_router, w_in [E, d_in_proj, d_model] (rows z | x | B | C | dt),
+    conv_w [d_conv_ch, k], conv_b [d_conv_ch], dt_bias / A_log / D [H], norm_w [d_inner],
+    w_out [E, d_model, d_inner]; float32, the bf16-stored ones exactly representable in bf16."""
+    E, Dm, De, H = cfg.n_experts, cfg.d_model, cfg.d_inner, cfg.n_heads
+    w: Dict[str, Optional[np.ndarray]] = {}
+    w["w_router"] = _store(cfg, _normal(cfg, _T_WR, (E, Dm), 0.02))
+    w["b_router"] = (np.asarray(cfg.router_bias, dtype=np.float32) if cfg.router_bias is not None else None)
+    w["w_in"] = _store(cfg, _normal(cfg, _T_WIN, (E, cfg.d_in_proj, Dm), cfg.weight_std))
+    lim = 1.0 / np.sqrt(cfg.d_conv)
+    w["conv_w"] = _rng(cfg, _T_CW).uniform(-lim, lim, (cfg.d_conv_ch, cfg.d_conv)).astype(np.float32)
+    w["conv_b"] = _rng(cfg, _T_CB).uniform(-lim, lim, (cfg.d_conv_ch,)).astype(np.float32)
+    # per head: time step log-uniform in [1e-3, 1e-1] (dt_bias is its inverse softplus), A uniform in [1, 16]
+    tau = np.exp(_rng(cfg, _T_DTB).uniform(np.log(1e-3), np.log(1e-1), (H,)))
+    w["dt_bias"] = (tau + np.log(-np.expm1(-tau))).astype(np.float32)
+    w["A_log"] = np.log(_rng(cfg, _T_WDT).uniform(1.0, 16.0, (H,))).astype(np.float32)
+    w["D"] = _rng(cfg, _T_WX).uniform(0.5, 1.5, (H,)).astype(np.float32)
+    w["norm_w"] = _rng(cfg, _T_NORM).uniform(0.7, 1.3, (De,)).astype(np.float32)
+    w["w_out"] = _store(cfg, _normal(cfg, _T_WOUT, (E, Dm, De), cfg.weight_std))
+    return w
+
+
+def make_mamba2_input(cfg: Mamba2Config) -> np.ndarray:
+    """x [B, L, d_model]."""
+    x = _normal(cfg, _T_X, (cfg.batch, cfg.seq_len, cfg.d_model), 1.0)
+    if cfg.rms_norm_x:
+        x /= np.sqrt(np.mean(np.square(x, dtype=np.float32), axis=-1, keepdims=True))
+    return _store(cfg, x)
