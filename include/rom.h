@@ -364,6 +364,83 @@ ROM_API int rom_hybrid_stack_forward(const rom_dims *dims, int32_t d_ff, const r
                              void *tmp, void *ws, size_t ws_bytes, void *ffn_ws, size_t ffn_ws_bytes,
                              void *hip_stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * RoM on a Mamba2 layer (Sec. 5.2, Table 3; the paragraph on streamlined SSMs: every major projection
+ * of the block becomes a mixture of experts under the one shared router).  The paper prints no
+ * equations for this variant; what is computed (readings: the published Mamba2 layer, routed the
+ * way Eq. (9)-(13) route the Mamba layer):
+ *
+ *   router      as in rom_layer_forward (Eq. (9))
+ *   in          zxbcdt[n,:] = sum_k w_in[idx[n,k]] x[n,:]        (unweighted sum, as Eq. (10)/(11));
+ *               columns z [d_inner] | x [d_inner] | B [d_state] | C [d_state] | dt [n_heads]
+ *   conv        x | B | C <- SiLU(conv_b + causal depthwise conv_4(x | B | C))
+ *   scan        per head h (headdim channels), dt = softplus(dt + dt_bias[h]), A = -exp(A_log[h]):
+ *               H <- exp(dt A) H + dt x B^T ;  y = H C + D[h] x          (H: headdim x d_state)
+ *   gate, norm  g = RMSNorm(y * SiLU(z)) * norm_w       (over all d_inner channels, eps inside the root)
+ *   out         out[n,:] = sum_k gate[n,k] * (w_out[idx[n,k]] g[n,:])              (as Eq. (12)/(13))
+ *
+ * Supported: ROM_DTYPE_BF16, headdim == 64, d_state in {64, 128}, d_conv == 4, d_inner a multiple of
+ * 512 (n_heads = d_inner / 64 a multiple of 8), d_model % 8 == 0, 1 <= top_k <= n_experts <= 64,
+ * top_k <= 8; sequences start from a zero state.  Anything else: ROM_E_UNSUPPORTED / ROM_E_INVAL. */
+typedef struct rom_mamba2_dims {
+  int32_t d_model;
+  int32_t d_inner;
+  int32_t d_state;        /* N                                               */
+  int32_t d_conv;         /* 4                                               */
+  int32_t headdim;        /* P; n_heads = d_inner / headdim                  */
+  int32_t n_experts;
+  int32_t top_k;
+  int32_t dtype;          /* ROM_DTYPE_BF16                                  */
+  int32_t gate_mode;      /* as rom_dims                                     */
+} rom_mamba2_dims;
+
+/* All pointers 16-byte aligned device pointers; "T" is bf16. */
+typedef struct rom_mamba2_weights {
+  const void  *w_router;  /* T   [E, d_model]                                                   */
+  const float *b_router;  /* f32 [E] or NULL                                                    */
+  const void  *w_in;      /* T   [E, 2*d_inner + 2*d_state + n_heads, d_model]; rows z | x | B | C | dt */
+  const float *conv_w;    /* f32 [d_inner + 2*d_state, 4] over the channels x | B | C           */
+  const float *conv_b;    /* f32 [d_inner + 2*d_state] or NULL                                  */
+  const float *dt_bias;   /* f32 [n_heads]                                                      */
+  const float *A_log;     /* f32 [n_heads]; A = -exp(A_log)                                     */
+  const float *D;         /* f32 [n_heads]                                                      */
+  const float *norm_w;    /* f32 [d_inner]                                                      */
+  const void  *w_out;     /* T   [E, d_model, d_inner]                                          */
+} rom_mamba2_weights;
+
+/* Byte offsets of the intermediates inside the workspace after rom_mamba2_forward. */
+typedef struct rom_mamba2_ws_layout {
+  size_t total_bytes;
+  size_t expert_idx;   /* i32 [N*K]                                        */
+  size_t gate;         /* f32 [N*K]                                        */
+  size_t counts;       /* i32 [E]                                          */
+  size_t offsets;      /* i32 [E+1]                                        */
+  size_t perm;         /* i32 [N*K]                                        */
+  size_t inv_perm;     /* i32 [N*K]                                        */
+  size_t logits;       /* f32 [N, E]                                       */
+  size_t zxbcdt;       /* T   [N, 2*d_inner + 2*d_state + n_heads]  (sum over k applied) */
+  size_t xbc;          /* T   [N, d_inner + 2*d_state]  after conv + SiLU  */
+  size_t yz;           /* T   [N, d_inner]  (y + D x) * SiLU(z)            */
+  size_t g;            /* T   [N, d_inner]  after the RMS norm             */
+} rom_mamba2_ws_layout;
+
+/* host-only; 0 / an error for invalid or unsupported dims */
+ROM_API size_t rom_mamba2_workspace_bytes(const rom_mamba2_dims *dims, int64_t B, int64_t L);
+ROM_API int rom_mamba2_workspace_layout(const rom_mamba2_dims *dims, int64_t B, int64_t L,
+                                        rom_mamba2_ws_layout *layout);
+
+/* The layer above on B sequences of L tokens, from zero states.
+ *   x, out   T [B, L, d_model] (distinct);  eps: the norm's epsilon (>= 0)
+ *   ws       rom_mamba2_workspace_bytes(dims, B, L), 256-byte aligned
+ * Asynchronous on hip_stream, allocates nothing; B * L == 0 is a successful no-op; errors are
+ * reported before anything is launched.  At most 2^30 (token, k) slots and 65535 sequences.
+ * With profiling on, the stages are recorded under ROM_STAGE_ROUTE, _PERMUTE, _IN_PROJ, _CONV,
+ * _SCAN (recurrence + gate), _DT_PROJ (the RMS norm: this layer has no dt projection), _OUT_PROJ,
+ * _COMBINE. */
+ROM_API int rom_mamba2_forward(const rom_mamba2_dims *dims, const rom_mamba2_weights *w, const void *x,
+                               int64_t B, int64_t L, float eps, void *out, void *ws, size_t ws_bytes,
+                               void *hip_stream);
+
 /* Static description of an error code. */
 ROM_API const char *rom_strerror(int code);
 

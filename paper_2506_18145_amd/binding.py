@@ -51,6 +51,22 @@ class _RomWsLayout(ctypes.Structure):
         "u", "dt_low", "bc", "dt", "g")]
 
 
+class RomMamba2Dims(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "d_model", "d_inner", "d_state", "d_conv", "headdim", "n_experts", "top_k", "dtype", "gate_mode")]
+
+
+class _RomMamba2Weights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in (
+        "w_router", "b_router", "w_in", "conv_w", "conv_b", "dt_bias", "A_log", "D", "norm_w", "w_out")]
+
+
+class _RomMamba2WsLayout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_size_t) for n in (
+        "total_bytes", "expert_idx", "gate", "counts", "offsets", "perm", "inv_perm", "logits", "zxbcdt", "xbc",
+        "yz", "g")]
+
+
 def load_library() -> ctypes.CDLL:
     """Loads librom.so; raises if it has not been built (there is no fallback path)."""
     global _lib
@@ -112,6 +128,14 @@ def load_library() -> ctypes.CDLL:
     lib.rom_hybrid_stack_forward.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, ctypes.POINTER(_RomBlock),
                                              ctypes.POINTER(_RomFfnWeights), ctypes.c_int, ctypes.c_int, F32, P,
                                              I64, I64, P, P, P, P, P, P, P, SZ, P, SZ, P]
+    lib.rom_mamba2_workspace_bytes.restype = SZ
+    lib.rom_mamba2_workspace_bytes.argtypes = [ctypes.POINTER(RomMamba2Dims), I64, I64]
+    lib.rom_mamba2_workspace_layout.restype = ctypes.c_int
+    lib.rom_mamba2_workspace_layout.argtypes = [ctypes.POINTER(RomMamba2Dims), I64, I64,
+                                                ctypes.POINTER(_RomMamba2WsLayout)]
+    lib.rom_mamba2_forward.restype = ctypes.c_int
+    lib.rom_mamba2_forward.argtypes = [ctypes.POINTER(RomMamba2Dims), ctypes.POINTER(_RomMamba2Weights), P, I64, I64,
+                                       F32, P, P, SZ, P]
     lib.rom_strerror.restype = ctypes.c_char_p
     lib.rom_strerror.argtypes = [ctypes.c_int]
     lib.rom_profile_enable.restype = ctypes.c_int
@@ -305,6 +329,27 @@ def rom_hybrid_stack_forward(dims, d_ff, blocks, ffns, ffn_pre_norm, eps, x, B, 
         _ptr(conv_state_in), _ptr(ssm_state_in), _ptr(out), _ptr(conv_state_out), _ptr(ssm_state_out),
         _ptr(tmp), _ptr(ws), _nbytes(ws), _ptr(ffn_ws), _nbytes(ffn_ws), _stream())
     _check(code, "rom_hybrid_stack_forward")
+
+
+def rom_mamba2_workspace_bytes(dims: RomMamba2Dims, B: int, L: int) -> int:
+    return int(load_library().rom_mamba2_workspace_bytes(ctypes.byref(dims), B, L))
+
+
+def rom_mamba2_workspace_layout(dims: RomMamba2Dims, B: int, L: int) -> Dict[str, int]:
+    lay = _RomMamba2WsLayout()
+    _check(load_library().rom_mamba2_workspace_layout(ctypes.byref(dims), B, L, ctypes.byref(lay)),
+           "rom_mamba2_workspace_layout")
+    return {n: int(getattr(lay, n)) for n, _ in _RomMamba2WsLayout._fields_}
+
+
+def rom_mamba2_forward(dims, weights, x, B, L, eps, out, ws):
+    ws_struct = _RomMamba2Weights()
+    for name, _ in _RomMamba2Weights._fields_:
+        setattr(ws_struct, name, _ptr(weights.get(name)))
+    code = load_library().rom_mamba2_forward(
+        ctypes.byref(dims), ctypes.byref(ws_struct), _ptr(x), B, L, eps, _ptr(out), _ptr(ws),
+        ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check(code, "rom_mamba2_forward")
 
 
 def rom_profile_enable(max_calls: int) -> None:
@@ -653,3 +698,69 @@ class RomHybridStack:
                                  B, L, conv_state, ssm_state, out, conv_out, ssm_out, self._tmp,
                                  self.layers[0].workspace(max(B, 1), max(L, 1)), self._ffn_ws)
         return (out, conv_out, ssm_out) if return_states else out
+
+
+class RomMamba2Layer:
+    """Holds the parameters of one RoM-on-Mamba2 layer on the GPU plus a workspace, and forwards to
+    rom_mamba2_forward."""
+
+    def __init__(self, cfg, weights_np, device="cuda:0", eps: float = 1e-5):
+        load_library()
+        if not torch.cuda.is_available():
+            raise RomError("RomMamba2Layer needs a GPU: librom has no CPU path")
+        if cfg.dtype != "bf16":
+            raise RomError("rom_mamba2_forward takes bf16 only")
+        self.device = torch.device(device)
+        self.tdtype = torch.bfloat16
+        self.eps = eps
+        self.dims = RomMamba2Dims(cfg.d_model, cfg.d_inner, cfg.d_state, cfg.d_conv, cfg.headdim, cfg.n_experts,
+                                  cfg.top_k, ROM_DTYPE_BF16, cfg.gate_mode)
+        typed = {"w_router", "w_in", "w_out"}
+        self.weights: Dict[str, Optional[torch.Tensor]] = {}
+        for name, arr in weights_np.items():
+            if arr is None:
+                self.weights[name] = None
+                continue
+            t = arr if isinstance(arr, torch.Tensor) else torch.from_numpy(arr)
+            t = t.to(self.tdtype) if name in typed else t.to(torch.float32)
+            self.weights[name] = t.to(self.device).contiguous()
+        self._ws: Optional[torch.Tensor] = None
+
+    def to_device(self, arr) -> torch.Tensor:
+        return torch.from_numpy(arr).to(self.tdtype).to(self.device).contiguous()
+
+    def workspace(self, B: int, L: int) -> torch.Tensor:
+        need = rom_mamba2_workspace_bytes(self.dims, B, L)
+        if need == 0:
+            raise RomError("rom_mamba2_workspace_bytes returned 0: unsupported dims")
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def ws_view(self, name: str, B: int, L: int) -> torch.Tensor:
+        """Intermediate tensor `name` of the last forward call with these B, L."""
+        lay = rom_mamba2_workspace_layout(self.dims, B, L)
+        d, n = self.dims, B * L
+        n_heads = d.d_inner // d.headdim
+        shapes = {
+            "expert_idx": (torch.int32, (n, d.top_k)), "gate": (torch.float32, (n, d.top_k)),
+            "counts": (torch.int32, (d.n_experts,)), "offsets": (torch.int32, (d.n_experts + 1,)),
+            "perm": (torch.int32, (n * d.top_k,)), "inv_perm": (torch.int32, (n * d.top_k,)),
+            "logits": (torch.float32, (n, d.n_experts)),
+            "zxbcdt": (self.tdtype, (n, 2 * d.d_inner + 2 * d.d_state + n_heads)),
+            "xbc": (self.tdtype, (n, d.d_inner + 2 * d.d_state)),
+            "yz": (self.tdtype, (n, d.d_inner)), "g": (self.tdtype, (n, d.d_inner)),
+        }
+        dtype, shape = shapes[name]
+        count = 1
+        for s in shape:
+            count *= s
+        nbytes = count * torch.empty((), dtype=dtype).element_size()
+        off = lay[name]
+        return self._ws[off:off + nbytes].view(dtype).view(shape)
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        B, L = int(x.shape[0]), int(x.shape[1])
+        out = torch.empty_like(x)
+        rom_mamba2_forward(self.dims, self.weights, x, B, L, self.eps, out, self.workspace(max(B, 1), max(L, 1)))
+        return out

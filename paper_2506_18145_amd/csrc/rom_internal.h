@@ -164,6 +164,22 @@ hipError_t launch_wgrad(int dtype, const void *A, int64_t lda, int M, const void
                         const int32_t *rows_a, const int32_t *rows_b, const float *row_scale, const int32_t *offsets,
                         int n_groups, int64_t n_pos, float *C, hipStream_t s);
 
+// ---------------------------------------------------------------- RoM on Mamba2 (rom_mamba2.hip; bf16 only)
+// Mamba2's recurrence per head of 64 channels with the D skip and the SiLU(z) gate:
+//   xbc bf16 [B*L, ld_xbc] holds x (head h at columns x_col + 64 h), B (b_col .. + d_state) and C (c_col ..)
+//   after conv + SiLU; dt_raw bf16 [B*L, ld_dt], column dt_col + h, before bias and softplus; z bf16
+//   [B*L, ld_z], head h at columns 64 h; dt_bias, A_log, D f32 [n_heads]; yz bf16 [B*L, ld_y] =
+//   (y + D x) * SiLU(z); carry: f32 scratch of ssd_carry_bytes()
+bool ssd_supported(int d_state, int headdim);
+size_t ssd_carry_bytes(int64_t B, int64_t L, int n_heads, int d_state);
+hipError_t launch_ssd_scan(const void *xbc, int64_t ld_xbc, int x_col, int b_col, int c_col, const void *dt_raw,
+                           int64_t ld_dt, int dt_col, const void *z, int64_t ld_z, const float *dt_bias,
+                           const float *A_log, const float *D, int64_t B, int64_t L, int n_heads, int d_state,
+                           float *carry, void *yz, int64_t ld_y, hipStream_t s);
+// out[n, :] = in[n, :] / sqrt(mean(in[n, :]^2) + eps) * w  (bf16 rows of n_cols, n_cols % 8 == 0; out may be in)
+hipError_t launch_rms_rows(const void *in, const float *w, float eps, int64_t n_rows, int n_cols, void *out,
+                           hipStream_t s);
+
 // timing probes (bench.py --probe): out is f32 scratch of n_blocks * 256 floats
 hipError_t launch_probe_issue(int op, int chains, int n_blocks, int iters, float *out, hipStream_t s);
 hipError_t launch_probe_scan(int parts, int lds, int n_blocks, int tiles, float *out, hipStream_t s);

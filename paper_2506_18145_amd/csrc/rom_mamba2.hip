@@ -1,0 +1,445 @@
+// RoM on a Mamba2 layer (Sec. 5.2, Table 3): the sequence part between the routed input and output
+// projections - Mamba2's recurrence per head
+//     H_t = exp(dt_t A) H_{t-1} + dt_t x_t B_t^T   (H: P x N),     y_t = H_t C_t + D x_t
+// followed by the SiLU(z) gate, and the RMS norm of the gated rows.  gfx950 only, bf16 activations.
+//
+// The recurrence runs in its chunked ("dual") form on the matrix cores: over a chunk of Q = 64 steps
+// with cum_t = sum_{r <= t} dt_r A inside the chunk,
+//     y_t   = exp(cum_t) C_t . H_prev + sum_{s <= t} (C_t . B_s) exp(cum_t - cum_s) (dt_s x_s)
+//     H_new = exp(cum_Q) H_prev + sum_s exp(cum_Q - cum_s) B_s (dt_s x_s)^T
+// which is four small matrix products per chunk (scores C B^T, scores x inputs, C x state, B^T x
+// inputs); every exponent is <= 0, so nothing overflows however strong the decay.  A workgroup
+// (4 wavefronts) owns one (sequence, head, segment of the sequence) and walks its chunks in order
+// with the state H in MFMA accumulators (fp32): wavefront w holds H[:, 16w .. 16w+15] and produces
+// the same 16 output channels, so the state never leaves its registers - as the B operand of
+// C x state it is read straight from the accumulators (the contraction index is permuted the same
+// way on the C side).  Sequences are cut into segments until there are two workgroups per CU; a
+// first pass (the same kernel without its output part) leaves every segment's end state from a
+// zero start and its total log decay, which the main pass folds in segment order.
+#include "rom_internal.h"
+
+#include <atomic>
+#include <mutex>
+
+namespace rom {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+
+constexpr int kQ = 64;          // steps per chunk
+constexpr int kP = 64;          // channels per head
+constexpr float kLog2e = 1.44269504088896341f;
+
+__device__ __forceinline__ float softplus_f32(float v) { return v > 20.0f ? v : log1pf(__expf(v)); }
+
+// LDS of one workgroup.  Rows are padded by 8 halfs (16 bytes): the 16-byte fragment reads of 16
+// consecutive rows then fall into different banks.
+template <int NS>
+struct SsdSmem {
+  union {
+    bf16_t b[kQ][NS + 8];       // B, step-major (operand of the scores)
+    float y[kQ][kP + 4];        // later in the chunk: the output tile, for row-wise stores
+  } u;
+  bf16_t c[kQ][NS + 8];         // C, step-major
+  bf16_t bw_t[NS][kQ + 8];      // exp(cum_Q - cum_s) B_s, state-major (operand of the state update)
+  bf16_t xd_t[kP][kQ + 8];      // dt_s x_s, channel-major
+  bf16_t g[kQ][kQ + 8];         // masked, decayed scores [t][s]
+  float cum[kQ], ecum[kQ];      // cum_t and exp(cum_t)
+};
+
+__device__ __forceinline__ float bf16_elem(const u32x4_t &v, int m) {      // element m (0..7) of 8 packed bf16
+  const unsigned int w = v[m >> 1];
+  return __uint_as_float((m & 1) ? (w & 0xFFFF0000u) : (w << 16));
+}
+
+// Eight 16-byte pieces (eight consecutive columns of eight consecutive steps), step i scaled by f[i],
+// to LDS column-major: for each of the eight columns the eight steps as one 16-byte row segment.
+template <int PITCH>
+__device__ __forceinline__ void park_scaled_8x8(const u32x4_t (&v)[8], const float (&f)[8], bf16_t (*dst)[PITCH], int col0,
+                                                int step0) {
+#pragma unroll
+  for (int m = 0; m < 8; ++m) {
+    u32x4_t seg;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+      seg[a] = pack_bf16x2(f[2 * a] * bf16_elem(v[2 * a], m), f[2 * a + 1] * bf16_elem(v[2 * a + 1], m));
+    *reinterpret_cast<u32x4_t *>(&dst[col0 + m][step0]) = seg;
+  }
+}
+
+__device__ __forceinline__ bf16x8_t as_frag(const u32x4_t &v) { return __builtin_bit_cast(bf16x8_t, v); }
+__device__ __forceinline__ bf16x8_t frag_from_halves(const u32x2_t &lo, const u32x2_t &hi) {
+  const u32x4_t v = {lo[0], lo[1], hi[0], hi[1]};
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// Grid (n_heads, B * n_seg).  CARRY: the state-only pass (segments before the last one).
+//   xbc   bf16 [B*L, ld_xbc]: x of head h at columns x_col + 64 h, B at b_col, C at c_col (after conv + SiLU)
+//   dt_raw bf16 [B*L, ld_dt]: column dt_col + h, before bias and softplus;   z bf16 [B*L, ld_z]: column 64 h
+//   carry_state f32 [B][n_seg][H][NS][64], carry_decay f32 [B][n_seg][H]
+//   yz    bf16 [B*L, ld_y]: (y + D x) * SiLU(z)
+template <int NS, bool CARRY>
+__global__ __launch_bounds__(256) void ssd_kernel(const bf16_t *__restrict__ xbc, int64_t ld_xbc, int x_col, int b_col,
+                                                  int c_col, const bf16_t *__restrict__ dt_raw, int64_t ld_dt,
+                                                  int dt_col, const bf16_t *__restrict__ z, int64_t ld_z,
+                                                  const float *__restrict__ dt_bias, const float *__restrict__ A_log,
+                                                  const float *__restrict__ Dp, int64_t L, int n_seg, int64_t seg_len,
+                                                  float *__restrict__ carry_state, float *__restrict__ carry_decay,
+                                                  bf16_t *__restrict__ yz, int64_t ld_y) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  SsdSmem<NS> &sm = *reinterpret_cast<SsdSmem<NS> *>(smem_raw);
+  constexpr int kNB = NS / 16;          // 16-row blocks of the state
+  constexpr int kKS = NS / 32;          // 32-wide steps of a contraction over the state index
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, c = lane & 15;
+  const int h = blockIdx.x, n_heads = gridDim.x;
+  const int64_t b = blockIdx.y / n_seg;
+  const int seg = static_cast<int>(blockIdx.y % n_seg);
+  if (CARRY && seg == n_seg - 1) return;            // nobody needs the last segment's end state
+  const int64_t ts = seg * seg_len, te = ts + seg_len < L ? ts + seg_len : L;
+  const float a = -__expf(A_log[h]);
+  const float bias = dt_bias[h];
+  const bf16_t *xbc_b = xbc + b * L * ld_xbc;
+  const bf16_t *dt_b = dt_raw + b * L * ld_dt + dt_col + h;
+  const int xc = x_col + h * kP;
+
+  // state: hacc[nb][r] = H[n = 16 nb + 4 g + r][p = 16 wave + c]
+  f32x4_t hacc[kNB];
+#pragma unroll
+  for (int nb = 0; nb < kNB; ++nb) hacc[nb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+  const int64_t carry_stride = static_cast<int64_t>(NS) * kP;
+  if (!CARRY) {
+    // fold the earlier segments' (decay, end state from zero) in order
+    for (int j = 0; j < seg; ++j) {
+      const int64_t unit = (b * n_seg + j) * n_heads + h;
+      const float dec = fast_exp2(carry_decay[unit] * kLog2e);
+      const float *sp = carry_state + unit * carry_stride + wave * 16 + c;
+#pragma unroll
+      for (int nb = 0; nb < kNB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) hacc[nb][r] = fmaf(dec, hacc[nb][r], sp[(16 * nb + 4 * g + r) * kP]);
+    }
+  }
+  float log_decay_total = 0.0f;
+
+  // roles while a chunk is parked: threads [0, NS) transpose B, the next 64 transpose x
+  const bool is_b = tid < NS;
+  const bool is_x = tid >= NS && tid < NS + 64;
+  const int lt = is_b ? tid : tid - NS;
+  const int so = lt & 7, co = lt >> 3;              // eight steps 8 so .., eight columns 8 co ..
+
+  for (int64_t t0 = ts; t0 < te; t0 += kQ) {
+    // time steps of the chunk, one per lane (every wavefront computes them for itself)
+    float dtv = 0.0f;
+    if (t0 + lane < te) dtv = softplus_f32(bf16_to_f32(dt_b[(t0 + lane) * ld_dt]) + bias);
+    float cum = dtv * a;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const float up = __shfl_up(cum, off);
+      if (lane >= off) cum += up;
+    }
+    const float cum_last = __shfl(cum, 63);
+    log_decay_total += cum_last;
+
+    __syncthreads();                // the chunk before this one is done with the LDS
+    if (is_b || is_x) {
+      u32x4_t v[8];
+      float f[8];
+      const int col = is_b ? b_col + 8 * co : xc + 8 * co;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int64_t t = t0 + 8 * so + i;
+        const int64_t tc = t < te ? t : te - 1;
+        v[i] = *reinterpret_cast<const u32x4_t *>(xbc_b + tc * ld_xbc + col);
+        if (t >= te) v[i] = u32x4_t{0u, 0u, 0u, 0u};
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float cs = __shfl(cum, 8 * so + i), ds = __shfl(dtv, 8 * so + i);
+        f[i] = is_b ? fast_exp2((cum_last - cs) * kLog2e) : ds;
+      }
+      if (is_b) {
+        if (!CARRY) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t *>(&sm.u.b[8 * so + i][8 * co]) = v[i];
+        }
+        park_scaled_8x8<kQ + 8>(v, f, sm.bw_t, 8 * co, 8 * so);
+      } else {
+        park_scaled_8x8<kQ + 8>(v, f, sm.xd_t, 8 * co, 8 * so);
+      }
+    }
+    if (!CARRY) {
+#pragma unroll
+      for (int i = 0; i < NS / 32; ++i) {           // C: 64 rows of NS / 8 pieces
+        const int piece = tid + 256 * i;
+        const int row = piece / (NS / 8), oc = piece % (NS / 8);
+        const int64_t t = t0 + row;
+        u32x4_t v = {0u, 0u, 0u, 0u};
+        if (t < te) v = *reinterpret_cast<const u32x4_t *>(xbc_b + t * ld_xbc + c_col + 8 * oc);
+        *reinterpret_cast<u32x4_t *>(&sm.c[row][8 * oc]) = v;
+      }
+      if (wave == 0) {
+        sm.cum[lane] = cum;
+        sm.ecum[lane] = fast_exp2(cum * kLog2e);
+      }
+    }
+    __syncthreads();
+
+    f32x4_t yacc[4];
+    if (!CARRY) {
+      // scores, this wavefront's 16 steps t = 16 wave + c against all s: G^T[s][t] = B_s . C_t, then the
+      // causal mask and the decay exp(cum_t - cum_s); stored [t][s]
+      const float cum_t = sm.cum[16 * wave + c];
+#pragma unroll
+      for (int sb = 0; sb < 4; ++sb) {
+        f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (sb <= wave) {
+#pragma unroll
+          for (int ks = 0; ks < kKS; ++ks) {
+            const bf16x8_t fa = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.u.b[16 * sb + c][32 * ks + 8 * g]));
+            const bf16x8_t fb = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.c[16 * wave + c][32 * ks + 8 * g]));
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, acc, 0, 0, 0);
+          }
+        }
+        const f32x4_t cum_s = *reinterpret_cast<const f32x4_t *>(&sm.cum[16 * sb + 4 * g]);
+        float val[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int s = 16 * sb + 4 * g + r, t = 16 * wave + c;
+          val[r] = s <= t ? acc[r] * fast_exp2((cum_t - cum_s[r]) * kLog2e) : 0.0f;
+        }
+        const u32x2_t packed = {pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3])};
+        *reinterpret_cast<u32x2_t *>(&sm.g[16 * wave + c][16 * sb + 4 * g]) = packed;
+      }
+      // contribution of the state the chunk starts from: Y[t][p] = exp(cum_t) sum_n C[t][n] H[n][p].
+      // The accumulators are the B operand as they are: slot (g, e) of a 32-wide step holds
+      // n = 32 ks + 4 g + e (e < 4) or 32 ks + 16 + 4 g + e - 4, and C is read in the same order.
+      bf16x8_t hop[kKS];
+#pragma unroll
+      for (int ks = 0; ks < kKS; ++ks) {
+        const u32x4_t hv = {pack_bf16x2(hacc[2 * ks][0], hacc[2 * ks][1]), pack_bf16x2(hacc[2 * ks][2], hacc[2 * ks][3]),
+                            pack_bf16x2(hacc[2 * ks + 1][0], hacc[2 * ks + 1][1]),
+                            pack_bf16x2(hacc[2 * ks + 1][2], hacc[2 * ks + 1][3])};
+        hop[ks] = as_frag(hv);
+      }
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb) {
+        yacc[tb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) {
+          const u32x2_t lo = *reinterpret_cast<const u32x2_t *>(&sm.c[16 * tb + c][32 * ks + 4 * g]);
+          const u32x2_t hi = *reinterpret_cast<const u32x2_t *>(&sm.c[16 * tb + c][32 * ks + 16 + 4 * g]);
+          yacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag_from_halves(lo, hi), hop[ks], yacc[tb], 0, 0, 0);
+        }
+        const f32x4_t e = *reinterpret_cast<const f32x4_t *>(&sm.ecum[16 * tb + 4 * g]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) yacc[tb][r] *= e[r];
+      }
+      __syncthreads();              // all scores are in LDS; nobody reads B's step-major copy any more
+    }
+
+    // dt_s x_s of this wavefront's 16 channels, all 64 steps: B operand of both remaining products
+    bf16x8_t xop[2];
+#pragma unroll
+    for (int k2 = 0; k2 < 2; ++k2)
+      xop[k2] = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.xd_t[16 * wave + c][32 * k2 + 8 * g]));
+    if (!CARRY) {
+      // inside the chunk: Y[t][p] += sum_{s <= t} G[t][s] (dt_s x_s[p]); steps 32.. only reach t >= 32
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2)
+          if (k2 == 0 || tb >= 2) {
+            const bf16x8_t fa = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.g[16 * tb + c][32 * k2 + 8 * g]));
+            yacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, xop[k2], yacc[tb], 0, 0, 0);
+          }
+    }
+    // state at the chunk's end: H = exp(cum_Q) H + sum_s (exp(cum_Q - cum_s) B_s) (dt_s x_s)^T
+    {
+      const float dec = fast_exp2(cum_last * kLog2e);
+#pragma unroll
+      for (int nb = 0; nb < kNB; ++nb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) hacc[nb][r] *= dec;
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+          const bf16x8_t fa = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.bw_t[16 * nb + c][32 * k2 + 8 * g]));
+          hacc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, xop[k2], hacc[nb], 0, 0, 0);
+        }
+      }
+    }
+    if (!CARRY) {
+      // output tile through LDS (over B's step-major copy) so that rows go out in 16-byte pieces,
+      // with the D skip and the SiLU(z) gate applied on the way
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sm.u.y[16 * tb + 4 * g + r][16 * wave + c] = yacc[tb][r];
+      __syncthreads();
+      const float d_skip = Dp[h];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int row = (tid >> 3) + 32 * i, po = tid & 7;
+        const int64_t t = t0 + row;
+        if (t < te) {
+          const int64_t n = b * L + t;
+          const u32x4_t xv = *reinterpret_cast<const u32x4_t *>(xbc_b + t * ld_xbc + xc + 8 * po);
+          const u32x4_t zv = *reinterpret_cast<const u32x4_t *>(z + n * ld_z + h * kP + 8 * po);
+          const f32x4_t y0 = *reinterpret_cast<const f32x4_t *>(&sm.u.y[row][8 * po]);
+          const f32x4_t y1 = *reinterpret_cast<const f32x4_t *>(&sm.u.y[row][8 * po + 4]);
+          float o[8];
+#pragma unroll
+          for (int m = 0; m < 8; ++m) {
+            const float yv = (m < 4 ? y0[m & 3] : y1[m & 3]) + d_skip * bf16_elem(xv, m);
+            o[m] = yv * silu_f32(bf16_elem(zv, m));
+          }
+          const u32x4_t ov = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]),
+                              pack_bf16x2(o[6], o[7])};
+          *reinterpret_cast<u32x4_t *>(yz + n * ld_y + h * kP + 8 * po) = ov;
+        }
+      }
+    }
+  }
+
+  if (CARRY) {
+    const int64_t unit = (b * n_seg + seg) * n_heads + h;
+    float *sp = carry_state + unit * carry_stride + wave * 16 + c;
+#pragma unroll
+    for (int nb = 0; nb < kNB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) sp[(16 * nb + 4 * g + r) * kP] = hacc[nb][r];
+    if (tid == 0) carry_decay[unit] = log_decay_total;
+  }
+}
+
+// g[n, :] = yz[n, :] / sqrt(mean(yz[n, :]^2) + eps) * w: one wavefront per row, fp32 sums
+__global__ __launch_bounds__(256) void rms_rows_kernel(const bf16_t *__restrict__ yz, const float *__restrict__ w,
+                                                       float eps, int64_t n_rows, int n_cols, bf16_t *__restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (row >= n_rows) return;
+  const bf16_t *src = yz + row * n_cols;
+  float ss = 0.0f;
+  for (int c0 = lane * 8; c0 < n_cols; c0 += 512) {
+    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(src + c0);
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      const float f = bf16_elem(v, m);
+      ss = fmaf(f, f, ss);
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+  const float rstd = rsqrtf(ss / static_cast<float>(n_cols) + eps);
+  bf16_t *dst = out + row * n_cols;
+  for (int c0 = lane * 8; c0 < n_cols; c0 += 512) {
+    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(src + c0);
+    const f32x4_t w0 = *reinterpret_cast<const f32x4_t *>(w + c0), w1 = *reinterpret_cast<const f32x4_t *>(w + c0 + 4);
+    float o[8];
+#pragma unroll
+    for (int m = 0; m < 8; ++m) o[m] = bf16_elem(v, m) * rstd * (m < 4 ? w0[m & 3] : w1[m & 3]);
+    const u32x4_t ov = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])};
+    *reinterpret_cast<u32x4_t *>(dst + c0) = ov;
+  }
+}
+
+struct SsdPlan {
+  int n_seg;
+  int64_t seg_len;
+};
+SsdPlan ssd_plan(int64_t B, int64_t L, int n_heads) {
+  // two workgroups for each of the 256 CUs; a segment is whole chunks and at least four of them
+  const int64_t chunks = ceil_div(L, kQ);
+  int64_t n_seg = ceil_div(512, B * n_heads);
+  const int64_t max_seg = chunks / 4 > 0 ? chunks / 4 : 1;
+  n_seg = n_seg < 1 ? 1 : (n_seg > max_seg ? max_seg : n_seg);
+  SsdPlan p;
+  p.seg_len = ceil_div(chunks, n_seg) * kQ;
+  p.n_seg = static_cast<int>(ceil_div(L, p.seg_len));
+  return p;
+}
+
+template <int NS, bool CARRY>
+hipError_t ssd_allow_lds() {
+  // more than 64 KiB of dynamic LDS: a function attribute, set once per device
+  static std::mutex mu;
+  static std::atomic<bool> done[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!done[dev].load(std::memory_order_acquire)) {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!done[dev].load(std::memory_order_relaxed)) {
+      e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ssd_kernel<NS, CARRY>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(SsdSmem<NS>)));
+      if (e != hipSuccess) return e;
+      done[dev].store(true, std::memory_order_release);
+    }
+  }
+  return hipSuccess;
+}
+
+template <int NS>
+hipError_t ssd_dispatch(const bf16_t *xbc, int64_t ld_xbc, int x_col, int b_col, int c_col, const bf16_t *dt_raw,
+                        int64_t ld_dt, int dt_col, const bf16_t *z, int64_t ld_z, const float *dt_bias,
+                        const float *A_log, const float *D, int64_t B, int64_t L, int n_heads, float *carry,
+                        bf16_t *yz, int64_t ld_y, hipStream_t s) {
+  const SsdPlan p = ssd_plan(B, L, n_heads);
+  float *carry_state = carry;
+  float *carry_decay = carry + static_cast<size_t>(B) * p.n_seg * n_heads * NS * kP;
+  const dim3 grid(static_cast<unsigned>(n_heads), static_cast<unsigned>(B * p.n_seg));
+  const size_t lds = sizeof(SsdSmem<NS>);
+  hipError_t e;
+  if (p.n_seg > 1) {
+    if ((e = ssd_allow_lds<NS, true>()) != hipSuccess) return e;
+    hipLaunchKernelGGL((ssd_kernel<NS, true>), grid, dim3(256), lds, s, xbc, ld_xbc, x_col, b_col, c_col, dt_raw, ld_dt,
+                       dt_col, z, ld_z, dt_bias, A_log, D, L, p.n_seg, p.seg_len, carry_state, carry_decay, yz, ld_y);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  if ((e = ssd_allow_lds<NS, false>()) != hipSuccess) return e;
+  hipLaunchKernelGGL((ssd_kernel<NS, false>), grid, dim3(256), lds, s, xbc, ld_xbc, x_col, b_col, c_col, dt_raw, ld_dt,
+                     dt_col, z, ld_z, dt_bias, A_log, D, L, p.n_seg, p.seg_len, carry_state, carry_decay, yz, ld_y);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t ssd_carry_bytes(int64_t B, int64_t L, int n_heads, int d_state) {
+  const SsdPlan p = ssd_plan(B, L, n_heads);
+  if (p.n_seg <= 1) return 0;
+  return static_cast<size_t>(B) * p.n_seg * n_heads * (static_cast<size_t>(d_state) * kP + 1) * sizeof(float);
+}
+
+bool ssd_supported(int d_state, int headdim) { return headdim == kP && (d_state == 64 || d_state == 128); }
+
+hipError_t launch_ssd_scan(const void *xbc, int64_t ld_xbc, int x_col, int b_col, int c_col, const void *dt_raw,
+                           int64_t ld_dt, int dt_col, const void *z, int64_t ld_z, const float *dt_bias,
+                           const float *A_log, const float *D, int64_t B, int64_t L, int n_heads, int d_state,
+                           float *carry, void *yz, int64_t ld_y, hipStream_t s) {
+  if (B * L <= 0) return hipSuccess;
+  if (B * ssd_plan(B, L, n_heads).n_seg > 65535) return hipErrorInvalidValue;
+  const bf16_t *xp = static_cast<const bf16_t *>(xbc), *dp = static_cast<const bf16_t *>(dt_raw);
+  const bf16_t *zp = static_cast<const bf16_t *>(z);
+  if (d_state == 128)
+    return ssd_dispatch<128>(xp, ld_xbc, x_col, b_col, c_col, dp, ld_dt, dt_col, zp, ld_z, dt_bias, A_log, D, B, L, n_heads,
+                             carry, static_cast<bf16_t *>(yz), ld_y, s);
+  if (d_state == 64)
+    return ssd_dispatch<64>(xp, ld_xbc, x_col, b_col, c_col, dp, ld_dt, dt_col, zp, ld_z, dt_bias, A_log, D, B, L, n_heads,
+                            carry, static_cast<bf16_t *>(yz), ld_y, s);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_rms_rows(const void *yz, const float *w, float eps, int64_t n_rows, int n_cols, void *out,
+                           hipStream_t s) {
+  if (n_rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(rms_rows_kernel, dim3(static_cast<unsigned>(ceil_div(n_rows, 4))), dim3(256), 0, s,
+                     static_cast<const bf16_t *>(yz), w, eps, n_rows, n_cols, static_cast<bf16_t *>(out));
+  return hipGetLastError();
+}
+
+}  // namespace rom
