@@ -401,6 +401,61 @@ def backward_rate(cfg, steps, warmup):
             "gemm_tflops_forward_plus_backward": 3.0 * gemm / (ms * 1e-3) / 1e12, "gradients_finite": finite}
 
 
+def mamba2_rate(steps, warmup):
+    """RoM on a Mamba2 layer (Sec. 5.2, Table 3) at the headline layer's size: rom_mamba2_forward on
+    B=1, L=16384, d_model 2048, 64 heads of 64 channels, state size 128, 8 experts top-1."""
+    import torch
+    from paper_2506_18145_amd import (RomMamba2Layer, rom_profile_collect_calls, rom_profile_enable,
+                                      rom_profile_select, STAGE_NAMES)
+    from rom_synth import get_mamba2_config, make_mamba2_input, make_mamba2_weights
+    cfg = get_mamba2_config("m2_cfg2")
+    layer = RomMamba2Layer(cfg, make_mamba2_weights(cfg), device="cuda:0")
+    x = layer.to_device(make_mamba2_input(cfg))
+    for _ in range(warmup):
+        layer.forward(x)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    evs[0].record()
+    for i in range(steps):
+        layer.forward(x)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    ms = _median([evs[i].elapsed_time(evs[i + 1]) for i in range(steps)])
+    # a second pass with an event at every stage boundary
+    rom_profile_select(0xFFFFFFFF)
+    rom_profile_enable(steps)
+    for _ in range(steps):
+        layer.forward(x)
+    torch.cuda.synchronize()
+    per_call = rom_profile_collect_calls(steps)
+    rom_profile_enable(0)
+    names = {"dt_proj": "rms_norm", "scan_gate": "ssd_scan_gate"}
+    stages = {}
+    for nm in STAGE_NAMES:
+        vals = [c[nm] for c in per_call if c[nm] > 0]
+        if vals:
+            stages[names.get(nm, nm)] = _median(vals)
+    n_tok = cfg.n_tokens
+    S = n_tok * cfg.top_k
+    gemm = 2.0 * S * cfg.d_model * cfg.d_in_proj + 2.0 * S * cfg.d_inner * cfg.d_model
+    # the recurrence per chunk of 64 steps and head: scores, scores x inputs, C x state, state update
+    ssd = n_tok / 64.0 * cfg.n_heads * 2.0 * (64 * 64 * cfg.d_state + 64 * 64 * 64 + 2 * 64 * cfg.d_state * 64)
+    out = {"workload": f"{cfg.name}: RoM on Mamba2, B={cfg.batch}, L={cfg.seq_len}, d_model={cfg.d_model}, "
+                       f"d_inner={cfg.d_inner}, headdim={cfg.headdim}, d_state={cfg.d_state}, E={cfg.n_experts}, "
+                       f"top_k={cfg.top_k}, bf16",
+           "ms_per_call": ms, "tokens_per_s": n_tok / (ms * 1e-3), "stages_ms": stages,
+           "gemm_tflops": gemm / (ms * 1e-3) / 1e12}
+    if "in_proj" in stages:
+        out["in_proj_frac_of_mfma_peak"] = 2.0 * S * cfg.d_model * cfg.d_in_proj / (stages["in_proj"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
+    if "ssd_scan_gate" in stages:
+        t = stages["ssd_scan_gate"] * 1e-3
+        # algorithmic bytes of the recurrence: x, B, C, dt, z read once, the gated output written once
+        byt = n_tok * 2.0 * (cfg.d_inner * 3 + 2 * cfg.d_state + cfg.n_heads)
+        out["ssd_scan"] = {"ms": stages["ssd_scan_gate"], "tflops": ssd / t / 1e12, "gbytes_per_s": byt / t / 1e9,
+                           "frac_of_hbm_peak": byt / t / 1e9 / PEAK_HBM_GBS}
+    return out
+
+
 def config_leg(name, steps, warmup):
     """The same measurement on another of the paper-shaped workloads (beside the headline one)."""
     from rom_synth import get_config
@@ -542,6 +597,7 @@ def main():
                     help="skip the extra measurement of the shared x/dt variant of the workload")
     ap.add_argument("--no-ffn", action="store_true", help="skip the extra FFN-MoE layer measurement")
     ap.add_argument("--no-backward", action="store_true", help="skip the extra backward-pass measurement")
+    ap.add_argument("--no-mamba2", action="store_true", help="skip the RoM-on-Mamba2 layer measurement")
     ap.add_argument("--no-configs", action="store_true", help="skip the legs on the other paper-shaped workloads")
     ap.add_argument("--no-traffic", action="store_true",
                     help="skip the two rocprofv3 counter runs that measure the dominant kernel's HBM traffic")
@@ -642,6 +698,8 @@ def main():
         extra("shared_xdt_variant", shared_leg)
     if not args.no_backward and cfg.top_k == 1:
         extra("backward", lambda: backward_rate(cfg, 5, 2))
+    if not args.no_mamba2:
+        extra("mamba2_variant", lambda: mamba2_rate(10, 3))
     if not args.no_ffn:
         extra("ffn_moe", lambda: ffn_moe_rate(cfg, 2 * cfg.d_model, 20, 20))
     if args.hybrid_layers > 0:

@@ -5,8 +5,8 @@
 //
 // The recurrence runs in its chunked ("dual") form on the matrix cores: over a chunk of Q = 64 steps
 // with cum_t = sum_{r <= t} dt_r A inside the chunk,
-//     y_t   = exp(cum_t) C_t . H_prev + sum_{s <= t} (C_t . B_s) exp(cum_t - cum_s) (dt_s x_s)
-//     H_new = exp(cum_Q) H_prev + sum_s exp(cum_Q - cum_s) B_s (dt_s x_s)^T
+//     y_t   = exp(cum_t) C_t . H_prev + sum_{s <= t} (C_t . B_s) exp(cum_t - cum_s) dt_s x_s
+//     H_new = exp(cum_Q) H_prev + sum_s exp(cum_Q - cum_s) dt_s B_s x_s^T
 // which is four small matrix products per chunk (scores C B^T, scores x inputs, C x state, B^T x
 // inputs); every exponent is <= 0, so nothing overflows however strong the decay.  A workgroup
 // (4 wavefronts) owns one (sequence, head, segment of the sequence) and walks its chunks in order
@@ -44,11 +44,27 @@ struct SsdSmem {
     float y[kQ][kP + 4];        // later in the chunk: the output tile, for row-wise stores
   } u;
   bf16_t c[kQ][NS + 8];         // C, step-major
-  bf16_t bw_t[NS][kQ + 8];      // exp(cum_Q - cum_s) B_s, state-major (operand of the state update)
-  bf16_t xd_t[kP][kQ + 8];      // dt_s x_s, channel-major
-  bf16_t g[kQ][kQ + 8];         // masked, decayed scores [t][s]
-  float cum[kQ], ecum[kQ];      // cum_t and exp(cum_t)
+  bf16_t bw_t[NS][kQ + 8];      // exp(cum_Q - cum_s) dt_s B_s, state-major (operand of the state update)
+  bf16_t xd_t[kP][kQ + 8];      // x, channel-major
+  bf16_t g[kQ][kQ + 8];         // masked, decayed, dt-weighted scores [t][s]
+  float cum[kQ], ecum[kQ], dt[kQ];   // cum_t, exp(cum_t), dt_t
 };
+
+// Inclusive prefix sum over the 64 lanes by DPP: shifts inside the rows of 16, then lane 15 of rows
+// 0 / 2 into rows 1 / 3 and lane 31 into rows 2 and 3.  Lanes a shift brings nothing to add zero.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_or_zero(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ float wave_inclusive_sum(float v) {
+  v += dpp_or_zero<0x111, 0xF>(v);      // row_shr:1
+  v += dpp_or_zero<0x112, 0xF>(v);      // row_shr:2
+  v += dpp_or_zero<0x114, 0xF>(v);      // row_shr:4
+  v += dpp_or_zero<0x118, 0xF>(v);      // row_shr:8
+  v += dpp_or_zero<0x142, 0xA>(v);      // row_bcast:15 into rows 1 and 3
+  v += dpp_or_zero<0x143, 0xC>(v);      // row_bcast:31 into rows 2 and 3
+  return v;
+}
 
 __device__ __forceinline__ float bf16_elem(const u32x4_t &v, int m) {      // element m (0..7) of 8 packed bf16
   const unsigned int w = v[m >> 1];
@@ -70,6 +86,24 @@ __device__ __forceinline__ void park_scaled_8x8(const u32x4_t (&v)[8], const flo
   }
 }
 
+// The same without scaling: word a of column m's segment holds steps 2a, 2a+1, which v_perm_b32
+// picks out of word m/2 of the two step rows.
+template <int PITCH>
+__device__ __forceinline__ void park_8x8(const u32x4_t (&v)[8], bf16_t (*dst)[PITCH], int col0, int step0) {
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {          // word w of a piece = columns 2w, 2w+1
+    u32x4_t lo, hi;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const unsigned int p0 = v[2 * a][w], p1 = v[2 * a + 1][w];
+      lo[a] = __builtin_amdgcn_perm(p1, p0, 0x05040100u);      // (p0.lo16, p1.lo16)
+      hi[a] = __builtin_amdgcn_perm(p1, p0, 0x07060302u);      // (p0.hi16, p1.hi16)
+    }
+    *reinterpret_cast<u32x4_t *>(&dst[col0 + 2 * w][step0]) = lo;
+    *reinterpret_cast<u32x4_t *>(&dst[col0 + 2 * w + 1][step0]) = hi;
+  }
+}
+
 __device__ __forceinline__ bf16x8_t as_frag(const u32x4_t &v) { return __builtin_bit_cast(bf16x8_t, v); }
 __device__ __forceinline__ bf16x8_t frag_from_halves(const u32x2_t &lo, const u32x2_t &hi) {
   const u32x4_t v = {lo[0], lo[1], hi[0], hi[1]};
@@ -82,7 +116,7 @@ __device__ __forceinline__ bf16x8_t frag_from_halves(const u32x2_t &lo, const u3
 //   carry_state f32 [B][n_seg][H][NS][64], carry_decay f32 [B][n_seg][H]
 //   yz    bf16 [B*L, ld_y]: (y + D x) * SiLU(z)
 template <int NS, bool CARRY>
-__global__ __launch_bounds__(256) void ssd_kernel(const bf16_t *__restrict__ xbc, int64_t ld_xbc, int x_col, int b_col,
+__global__ __launch_bounds__(256, 2) void ssd_kernel(const bf16_t *__restrict__ xbc, int64_t ld_xbc, int x_col, int b_col,
                                                   int c_col, const bf16_t *__restrict__ dt_raw, int64_t ld_dt,
                                                   int dt_col, const bf16_t *__restrict__ z, int64_t ld_z,
                                                   const float *__restrict__ dt_bias, const float *__restrict__ A_log,
@@ -130,69 +164,140 @@ __global__ __launch_bounds__(256) void ssd_kernel(const bf16_t *__restrict__ xbc
   const bool is_b = tid < NS;
   const bool is_x = tid >= NS && tid < NS + 64;
   const int lt = is_b ? tid : tid - NS;
-  const int so = lt & 7, co = lt >> 3;              // eight steps 8 so .., eight columns 8 co ..
+  // eight steps 8 so .., eight columns 8 co ..; consecutive lanes take consecutive column blocks of
+  // the same steps (whole rows per request, and the step-major copy of B lands in distinct banks)
+  const int n_co = is_b ? NS / 8 : kP / 8;
+  const int so = lt / n_co, co = lt % n_co;
+  // The channel-major arrays keep their 16-byte step pieces in swizzled order: piece j of row r
+  // sits at position j ^ ((r >> 3) & 7), so that the eight lanes that write the same steps of eight
+  // different column blocks (rows 8 apart: the same banks otherwise) hit distinct banks.
+  const int so_phys = so ^ (co & 7);
+  const int t_col = is_b ? b_col + 8 * co : xc + 8 * co;
+  // output rows: a wavefront stores the 16 channels it computed, two 8-channel pieces per step
+  const int e_row = lane >> 1, e_po = 2 * wave + (lane & 1);
+
+  // A chunk's inputs are requested one chunk ahead (rows beyond the segment's end: the last valid
+  // row, zeroed when parked - no branch around a load, so that the requests go out back to back):
+  // what the parking needs right after the chunk before has been parked, what the output rows need
+  // (x for the D skip, z) after the chunk before has been stored.
+  u32x4_t pv[8], pc[NS / 32], ex[2], ez[2];
+  unsigned short p_dt = 0;
+  // this thread's rows in the chunk to fetch next; the pointers advance by a chunk per fetch (no
+  // 64-bit multiplies per row), and only the segment's last, ragged chunk takes the clamped path
+  const bf16_t *dt_ptr = dt_b + (ts + lane) * ld_dt;
+  const bf16_t *pv_ptr = xbc_b + (ts + 8 * so) * ld_xbc + t_col;
+  const bf16_t *pc_ptr[NS / 32];
+#pragma unroll
+  for (int i = 0; i < NS / 32; ++i) {               // C: 64 rows of NS / 8 pieces
+    const int piece = tid + 256 * i;
+    pc_ptr[i] = xbc_b + (ts + piece / (NS / 8)) * ld_xbc + c_col + 8 * (piece % (NS / 8));
+  }
+  const bf16_t *ex_ptr = xbc_b + (ts + e_row) * ld_xbc + xc + 8 * e_po;
+  const bf16_t *ez_ptr = z + (b * L + ts + e_row) * ld_z + h * kP + 8 * e_po;
+  auto fetch_main = [&](int64_t t0) {
+    if (t0 >= te) return;
+    if (t0 + kQ <= te) {
+      p_dt = *dt_ptr;
+      if (is_b || is_x) {
+        const bf16_t *row = pv_ptr;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          pv[i] = *reinterpret_cast<const u32x4_t *>(row);
+          row += ld_xbc;
+        }
+      }
+      if (!CARRY) {
+#pragma unroll
+        for (int i = 0; i < NS / 32; ++i) pc[i] = *reinterpret_cast<const u32x4_t *>(pc_ptr[i]);
+      }
+    } else {
+      const int64_t last = te - 1 - t0;               // last valid row of the chunk
+      p_dt = dt_ptr[(lane <= last ? 0 : last - lane) * ld_dt];
+      if (is_b || is_x) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int64_t r = 8 * so + i;
+          pv[i] = *reinterpret_cast<const u32x4_t *>(pv_ptr + (r <= last ? i : last - 8 * so) * ld_xbc);
+        }
+      }
+      if (!CARRY) {
+#pragma unroll
+        for (int i = 0; i < NS / 32; ++i) {
+          const int64_t r = (tid + 256 * i) / (NS / 8);
+          pc[i] = *reinterpret_cast<const u32x4_t *>(pc_ptr[i] + (r <= last ? 0 : last - r) * ld_xbc);
+        }
+      }
+    }
+    dt_ptr += kQ * ld_dt;
+    pv_ptr += kQ * ld_xbc;
+#pragma unroll
+    for (int i = 0; i < NS / 32; ++i) pc_ptr[i] += kQ * ld_xbc;
+  };
+  auto fetch_out = [&](int64_t t0) {
+    if (CARRY || t0 >= te) return;
+    const int64_t last = te - 1 - t0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int64_t r = e_row + 32 * i;
+      const int64_t back = r <= last ? r - e_row : last - e_row;      // rows relative to this thread's first
+      ex[i] = *reinterpret_cast<const u32x4_t *>(ex_ptr + back * ld_xbc);
+      ez[i] = *reinterpret_cast<const u32x4_t *>(ez_ptr + back * ld_z);
+    }
+    ex_ptr += kQ * ld_xbc;
+    ez_ptr += kQ * ld_z;
+  };
+  fetch_main(ts);
+  fetch_out(ts);
 
   for (int64_t t0 = ts; t0 < te; t0 += kQ) {
     // time steps of the chunk, one per lane (every wavefront computes them for itself)
     float dtv = 0.0f;
-    if (t0 + lane < te) dtv = softplus_f32(bf16_to_f32(dt_b[(t0 + lane) * ld_dt]) + bias);
-    float cum = dtv * a;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const float up = __shfl_up(cum, off);
-      if (lane >= off) cum += up;
-    }
-    const float cum_last = __shfl(cum, 63);
+    if (t0 + lane < te) dtv = softplus_f32(bf16_to_f32(p_dt) + bias);
+    const float cum = wave_inclusive_sum(dtv * a);
+    const float cum_last = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cum), 63));
     log_decay_total += cum_last;
 
     __syncthreads();                // the chunk before this one is done with the LDS
     if (is_b || is_x) {
-      u32x4_t v[8];
-      float f[8];
-      const int col = is_b ? b_col + 8 * co : xc + 8 * co;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int64_t t = t0 + 8 * so + i;
-        const int64_t tc = t < te ? t : te - 1;
-        v[i] = *reinterpret_cast<const u32x4_t *>(xbc_b + tc * ld_xbc + col);
-        if (t >= te) v[i] = u32x4_t{0u, 0u, 0u, 0u};
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float cs = __shfl(cum, 8 * so + i), ds = __shfl(dtv, 8 * so + i);
-        f[i] = is_b ? fast_exp2((cum_last - cs) * kLog2e) : ds;
-      }
+      for (int i = 0; i < 8; ++i)
+        if (t0 + 8 * so + i >= te) pv[i] = u32x4_t{0u, 0u, 0u, 0u};
       if (is_b) {
+        // this lane's weight w_s = exp(cum_Q - cum_s) dt_s; the eight steps of the block come from their lanes
+        const float w_lane = fast_exp2((cum_last - cum) * kLog2e) * dtv;
+        float f[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = __shfl(w_lane, 8 * so + i);
         if (!CARRY) {
 #pragma unroll
-          for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t *>(&sm.u.b[8 * so + i][8 * co]) = v[i];
+          for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t *>(&sm.u.b[8 * so + i][8 * co]) = pv[i];
         }
-        park_scaled_8x8<kQ + 8>(v, f, sm.bw_t, 8 * co, 8 * so);
+        park_scaled_8x8<kQ + 8>(pv, f, sm.bw_t, 8 * co, 8 * so_phys);
       } else {
-        park_scaled_8x8<kQ + 8>(v, f, sm.xd_t, 8 * co, 8 * so);
+        park_8x8<kQ + 8>(pv, sm.xd_t, 8 * co, 8 * so_phys);
       }
     }
     if (!CARRY) {
 #pragma unroll
-      for (int i = 0; i < NS / 32; ++i) {           // C: 64 rows of NS / 8 pieces
+      for (int i = 0; i < NS / 32; ++i) {
         const int piece = tid + 256 * i;
-        const int row = piece / (NS / 8), oc = piece % (NS / 8);
-        const int64_t t = t0 + row;
-        u32x4_t v = {0u, 0u, 0u, 0u};
-        if (t < te) v = *reinterpret_cast<const u32x4_t *>(xbc_b + t * ld_xbc + c_col + 8 * oc);
-        *reinterpret_cast<u32x4_t *>(&sm.c[row][8 * oc]) = v;
+        const int row = piece / (NS / 8);
+        if (t0 + row >= te) pc[i] = u32x4_t{0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4_t *>(&sm.c[row][8 * (piece % (NS / 8))]) = pc[i];
       }
-      if (wave == 0) {
+      if (wave == 3) {                // the wavefront with no block to transpose
         sm.cum[lane] = cum;
         sm.ecum[lane] = fast_exp2(cum * kLog2e);
+        sm.dt[lane] = dtv;
       }
     }
     __syncthreads();
+    fetch_main(t0 + kQ);
 
     f32x4_t yacc[4];
     if (!CARRY) {
       // scores, this wavefront's 16 steps t = 16 wave + c against all s: G^T[s][t] = B_s . C_t, then the
-      // causal mask and the decay exp(cum_t - cum_s); stored [t][s]
+      // causal mask, the decay exp(cum_t - cum_s) and the step size dt_s; stored [t][s]
       const float cum_t = sm.cum[16 * wave + c];
 #pragma unroll
       for (int sb = 0; sb < 4; ++sb) {
@@ -206,11 +311,12 @@ __global__ __launch_bounds__(256) void ssd_kernel(const bf16_t *__restrict__ xbc
           }
         }
         const f32x4_t cum_s = *reinterpret_cast<const f32x4_t *>(&sm.cum[16 * sb + 4 * g]);
+        const f32x4_t dt_s = *reinterpret_cast<const f32x4_t *>(&sm.dt[16 * sb + 4 * g]);
         float val[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int s = 16 * sb + 4 * g + r, t = 16 * wave + c;
-          val[r] = s <= t ? acc[r] * fast_exp2((cum_t - cum_s[r]) * kLog2e) : 0.0f;
+          val[r] = s <= t ? acc[r] * dt_s[r] * fast_exp2((cum_t - cum_s[r]) * kLog2e) : 0.0f;
         }
         const u32x2_t packed = {pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3])};
         *reinterpret_cast<u32x2_t *>(&sm.g[16 * wave + c][16 * sb + 4 * g]) = packed;
@@ -242,13 +348,13 @@ __global__ __launch_bounds__(256) void ssd_kernel(const bf16_t *__restrict__ xbc
       __syncthreads();              // all scores are in LDS; nobody reads B's step-major copy any more
     }
 
-    // dt_s x_s of this wavefront's 16 channels, all 64 steps: B operand of both remaining products
+    // x of this wavefront's 16 channels, all 64 steps: B operand of both remaining products
     bf16x8_t xop[2];
 #pragma unroll
     for (int k2 = 0; k2 < 2; ++k2)
-      xop[k2] = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.xd_t[16 * wave + c][32 * k2 + 8 * g]));
+      xop[k2] = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.xd_t[16 * wave + c][8 * ((4 * k2 + g) ^ ((2 * wave + (c >> 3)) & 7))]));
     if (!CARRY) {
-      // inside the chunk: Y[t][p] += sum_{s <= t} G[t][s] (dt_s x_s[p]); steps 32.. only reach t >= 32
+      // inside the chunk: Y[t][p] += sum_{s <= t} G[t][s] x_s[p]; steps 32.. only reach t >= 32
 #pragma unroll
       for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
@@ -258,7 +364,7 @@ __global__ __launch_bounds__(256) void ssd_kernel(const bf16_t *__restrict__ xbc
             yacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, xop[k2], yacc[tb], 0, 0, 0);
           }
     }
-    // state at the chunk's end: H = exp(cum_Q) H + sum_s (exp(cum_Q - cum_s) B_s) (dt_s x_s)^T
+    // state at the chunk's end: H = exp(cum_Q) H + sum_s (exp(cum_Q - cum_s) dt_s B_s) x_s^T
     {
       const float dec = fast_exp2(cum_last * kLog2e);
 #pragma unroll
@@ -267,41 +373,37 @@ __global__ __launch_bounds__(256) void ssd_kernel(const bf16_t *__restrict__ xbc
         for (int r = 0; r < 4; ++r) hacc[nb][r] *= dec;
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2) {
-          const bf16x8_t fa = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.bw_t[16 * nb + c][32 * k2 + 8 * g]));
+          const bf16x8_t fa = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.bw_t[16 * nb + c][8 * ((4 * k2 + g) ^ ((2 * nb + (c >> 3)) & 7))]));
           hacc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, xop[k2], hacc[nb], 0, 0, 0);
         }
       }
     }
     if (!CARRY) {
-      // output tile through LDS (over B's step-major copy) so that rows go out in 16-byte pieces,
-      // with the D skip and the SiLU(z) gate applied on the way
+      // output tile through LDS (over B's step-major copy) so that rows go out in 16-byte pieces, with
+      // the D skip and the SiLU(z) gate applied on the way; a wavefront reads back only the 16
+      // columns it wrote itself, so no barrier is needed between the two
 #pragma unroll
       for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
         for (int r = 0; r < 4; ++r) sm.u.y[16 * tb + 4 * g + r][16 * wave + c] = yacc[tb][r];
-      __syncthreads();
       const float d_skip = Dp[h];
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const int row = (tid >> 3) + 32 * i, po = tid & 7;
+        const int row = e_row + 32 * i;
         const int64_t t = t0 + row;
-        if (t < te) {
-          const int64_t n = b * L + t;
-          const u32x4_t xv = *reinterpret_cast<const u32x4_t *>(xbc_b + t * ld_xbc + xc + 8 * po);
-          const u32x4_t zv = *reinterpret_cast<const u32x4_t *>(z + n * ld_z + h * kP + 8 * po);
-          const f32x4_t y0 = *reinterpret_cast<const f32x4_t *>(&sm.u.y[row][8 * po]);
-          const f32x4_t y1 = *reinterpret_cast<const f32x4_t *>(&sm.u.y[row][8 * po + 4]);
-          float o[8];
+        const f32x4_t y0 = *reinterpret_cast<const f32x4_t *>(&sm.u.y[row][8 * e_po]);
+        const f32x4_t y1 = *reinterpret_cast<const f32x4_t *>(&sm.u.y[row][8 * e_po + 4]);
+        float o[8];
 #pragma unroll
-          for (int m = 0; m < 8; ++m) {
-            const float yv = (m < 4 ? y0[m & 3] : y1[m & 3]) + d_skip * bf16_elem(xv, m);
-            o[m] = yv * silu_f32(bf16_elem(zv, m));
-          }
-          const u32x4_t ov = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]),
-                              pack_bf16x2(o[6], o[7])};
-          *reinterpret_cast<u32x4_t *>(yz + n * ld_y + h * kP + 8 * po) = ov;
+        for (int m = 0; m < 8; ++m) {
+          const float yv = (m < 4 ? y0[m & 3] : y1[m & 3]) + d_skip * bf16_elem(ex[i], m);
+          o[m] = yv * silu_f32(bf16_elem(ez[i], m));
         }
+        const u32x4_t ov = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]),
+                            pack_bf16x2(o[6], o[7])};
+        if (t < te) *reinterpret_cast<u32x4_t *>(yz + (b * L + t) * ld_y + h * kP + 8 * e_po) = ov;
       }
+      fetch_out(t0 + kQ);
     }
   }
 
