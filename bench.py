@@ -10,7 +10,8 @@ events around the dominant kernel (the in projection) only; the per-stage breakd
 second pass with an event at every stage boundary.  Beside the headline: HBM traffic of the
 dominant kernel from two rocprofv3 counter runs of this script, forward timings of the two other
 layer configurations, the load-balance statistics, the shared x/dt variant, forward + backward of
-the layer, a 48-block stack, the FFN-MoE layer, the recurrent step and the CPU oracle's rate
+the layer, RoM on a Mamba2 layer of the same size, a 48-block stack, the FFN-MoE layer, the
+recurrent step and the CPU oracle's rate
 (--help lists the switches that skip them; --probe prints issue-rate measurements instead).
 """
 import argparse

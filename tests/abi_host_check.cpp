@@ -137,6 +137,44 @@ int main() {
     CHECK(rom_backward_workspace_bytes(&d2, 1, 64) > rom_workspace_bytes(&d2, 1, 64));
   }
 
+  // ---- RoM on Mamba2: planning and validation
+  {
+    rom_mamba2_dims m;
+    m.d_model = 2048; m.d_inner = 4096; m.d_state = 128; m.d_conv = 4; m.headdim = 64;
+    m.n_experts = 8; m.top_k = 1; m.dtype = ROM_DTYPE_BF16; m.gate_mode = 0;
+    for (int64_t B : {int64_t(1), int64_t(3), int64_t(4096)})
+      for (int64_t L : {int64_t(1), int64_t(63), int64_t(16384), int64_t(1) << 17}) {
+        if (B * L > (int64_t(1) << 24)) continue;
+        const size_t bytes = rom_mamba2_workspace_bytes(&m, B, L);
+        CHECK(bytes > 0);
+        rom_mamba2_ws_layout lay;
+        CHECK(rom_mamba2_workspace_layout(&m, B, L, &lay) == ROM_OK);
+        CHECK(lay.total_bytes == bytes && lay.zxbcdt < bytes && lay.xbc < bytes && lay.yz < bytes && lay.g < bytes);
+        CHECK(lay.zxbcdt % 256 == 0 && lay.g % 256 == 0);
+      }
+    rom_mamba2_dims bad = m;
+    bad.d_state = 32;    CHECK(rom_mamba2_workspace_bytes(&bad, 1, 64) == 0);  bad = m;
+    bad.headdim = 32;    CHECK(rom_mamba2_workspace_bytes(&bad, 1, 64) == 0);  bad = m;
+    bad.dtype = ROM_DTYPE_F32;  CHECK(rom_mamba2_workspace_bytes(&bad, 1, 64) == 0);  bad = m;
+    bad.d_inner = 4096 + 64;    CHECK(rom_mamba2_workspace_bytes(&bad, 1, 64) == 0);  bad = m;
+    bad.top_k = 9;       CHECK(rom_mamba2_workspace_bytes(&bad, 1, 64) == 0);
+    CHECK(rom_mamba2_workspace_bytes(nullptr, 1, 64) == 0);
+    rom_mamba2_ws_layout lay;
+    CHECK(rom_mamba2_workspace_layout(&m, 1, 64, nullptr) == ROM_E_INVAL);
+    bad = m; bad.d_conv = 3;
+    CHECK(rom_mamba2_workspace_layout(&bad, 1, 64, &lay) == ROM_E_UNSUPPORTED);
+    rom_mamba2_weights mw;
+    std::memset(&mw, 0, sizeof(mw));
+    CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, 1e-5f, addr + 4096, addr, 4096, nullptr) == ROM_E_INVAL);   // NULL weights
+    mw.w_router = addr; mw.w_in = addr; mw.conv_w = reinterpret_cast<const float *>(addr);
+    mw.dt_bias = mw.A_log = mw.D = mw.norm_w = reinterpret_cast<const float *>(addr); mw.w_out = addr;
+    CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, 1e-5f, addr + 4096, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+    CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, -1.0f, addr + 4096, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_mamba2_forward(&m, &mw, addr, 0, 64, 1e-5f, addr + 4096, addr, 4096, nullptr) == ROM_OK);
+    CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, 1e-5f, addr, addr, 4096, nullptr) == ROM_E_INVAL);          // out == x
+    CHECK(rom_mamba2_forward(nullptr, &mw, addr, 1, 64, 1e-5f, addr + 4096, addr, 4096, nullptr) == ROM_E_INVAL);
+  }
+
   // ---- strings and the profiling bookkeeping
   CHECK(std::strcmp(rom_strerror(ROM_OK), "ok") == 0);
   for (int code : {ROM_E_INVAL, ROM_E_WORKSPACE, ROM_E_UNSUPPORTED, ROM_E_HIP, ROM_E_STATIC_LIMIT, -99})
