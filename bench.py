@@ -446,6 +446,29 @@ def mamba2_rate(steps, warmup):
                        f"top_k={cfg.top_k}, bf16",
            "ms_per_call": ms, "tokens_per_s": n_tok / (ms * 1e-3), "stages_ms": stages,
            "gemm_tflops": gemm / (ms * 1e-3) / 1e12}
+    # the recurrent form: one new token for each of 256 sequences, states updated in place
+    n_seq = 256
+    xs = layer.to_device(make_mamba2_input(cfg)[0, :n_seq].copy())
+    cs_shape, ss_shape = layer.state_shapes(n_seq)
+    cs = torch.zeros(cs_shape, device="cuda:0")
+    ss = torch.zeros(ss_shape, device="cuda:0")
+    out_step = torch.empty_like(xs)
+    for _ in range(10):
+        layer.step(xs, cs, ss, out=out_step)
+    torch.cuda.synchronize()
+    n_steps = 50
+    evs[0].record()
+    for _ in range(n_steps):
+        layer.step(xs, cs, ss, out=out_step)
+    evs[1].record()
+    torch.cuda.synchronize()
+    ms_step = evs[0].elapsed_time(evs[1]) / n_steps
+    w_bytes = 2.0 * cfg.n_experts * (cfg.d_in_proj * cfg.d_model + cfg.d_model * cfg.d_inner)
+    s_bytes = 2.0 * 4.0 * n_seq * cfg.n_heads * cfg.d_state * cfg.headdim
+    out["decode_step"] = {"workload": f"rom_mamba2_step, {n_seq} sequences", "ms_per_step": ms_step,
+                          "tokens_per_s": n_seq / (ms_step * 1e-3), "bound": "hbm",
+                          "algorithmic_gbytes_per_s": (w_bytes + s_bytes) / (ms_step * 1e-3) / 1e9,
+                          "frac": (w_bytes + s_bytes) / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS}
     if "in_proj" in stages:
         out["in_proj_frac_of_mfma_peak"] = 2.0 * S * cfg.d_model * cfg.d_in_proj / (stages["in_proj"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
     if "ssd_scan_gate" in stages:

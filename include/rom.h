@@ -381,7 +381,7 @@ ROM_API int rom_hybrid_stack_forward(const rom_dims *dims, int32_t d_ff, const r
  *
  * Supported: ROM_DTYPE_BF16, headdim == 64, d_state in {64, 128}, d_conv == 4, d_inner a multiple of
  * 512 (n_heads = d_inner / 64 a multiple of 8), d_model % 8 == 0, 1 <= top_k <= n_experts <= 64,
- * top_k <= 8; sequences start from a zero state.  Anything else: ROM_E_UNSUPPORTED / ROM_E_INVAL. */
+ * top_k <= 8.  Anything else: ROM_E_UNSUPPORTED / ROM_E_INVAL. */
 typedef struct rom_mamba2_dims {
   int32_t d_model;
   int32_t d_inner;
@@ -429,17 +429,32 @@ ROM_API size_t rom_mamba2_workspace_bytes(const rom_mamba2_dims *dims, int64_t B
 ROM_API int rom_mamba2_workspace_layout(const rom_mamba2_dims *dims, int64_t B, int64_t L,
                                         rom_mamba2_ws_layout *layout);
 
-/* The layer above on B sequences of L tokens, from zero states.
- *   x, out   T [B, L, d_model] (distinct);  eps: the norm's epsilon (>= 0)
- *   ws       rom_mamba2_workspace_bytes(dims, B, L), 256-byte aligned
+/* The layer above on B sequences of L tokens.
+ *   x, out          T [B, L, d_model] (distinct);  eps: the norm's epsilon (>= 0)
+ *   conv_state_in   f32 [B, d_inner + 2*d_state, 3] or NULL (zeros): the conv's inputs (x | B | C
+ *                   channels) at the three steps before the first, oldest first
+ *   ssm_state_in    f32 [B, n_heads, d_state, headdim] or NULL (zeros): H before the first step
+ *   conv_state_out, ssm_state_out   the same after the last step, or NULL (not wanted).  An output
+ *                   state may be the same buffer as its input only for L <= 32.
+ *   ws              rom_mamba2_workspace_bytes(dims, B, L), 256-byte aligned
  * Asynchronous on hip_stream, allocates nothing; B * L == 0 is a successful no-op; errors are
  * reported before anything is launched.  At most 2^30 (token, k) slots and 65535 sequences.
  * With profiling on, the stages are recorded under ROM_STAGE_ROUTE, _PERMUTE, _IN_PROJ, _CONV,
  * _SCAN (recurrence + gate), _DT_PROJ (the RMS norm: this layer has no dt projection), _OUT_PROJ,
  * _COMBINE. */
 ROM_API int rom_mamba2_forward(const rom_mamba2_dims *dims, const rom_mamba2_weights *w, const void *x,
-                               int64_t B, int64_t L, float eps, void *out, void *ws, size_t ws_bytes,
-                               void *hip_stream);
+                               int64_t B, int64_t L, float eps, const float *conv_state_in,
+                               const float *ssm_state_in, void *out, float *conv_state_out,
+                               float *ssm_state_out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* One new token for each of B sequences (the recurrent form of the layer above): x, out T [B, d_model];
+ * conv_state and ssm_state (layouts above, both required) are read and updated in place.
+ *   ws   rom_mamba2_workspace_bytes(dims, B, 1)
+ * The state is 8 * d_state / 16 times the Mamba layer's (d_state 128: 2 MiB per sequence at d_inner
+ * 4096); one call reads and writes it once. */
+ROM_API int rom_mamba2_step(const rom_mamba2_dims *dims, const rom_mamba2_weights *w, const void *x,
+                            int64_t B, float eps, float *conv_state, float *ssm_state, void *out,
+                            void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Static description of an error code. */
 ROM_API const char *rom_strerror(int code);

@@ -74,8 +74,10 @@ def gated_rms_norm(y, z, weight, eps):
 
 
 def rom_mamba2_forward(x, w: Dict[str, Optional[np.ndarray]], top_k: int, gate_mode: int, headdim: int,
-                       eps: float = 1e-5, expert_idx=None) -> Dict[str, np.ndarray]:
-    """x [B, L, d_model] -> out [B, L, d_model] and the intermediates (token-major, [N, ...])."""
+                       eps: float = 1e-5, expert_idx=None, conv_state=None, ssm_state=None) -> Dict[str, np.ndarray]:
+    """x [B, L, d_model] -> out [B, L, d_model] and the intermediates (token-major, [N, ...]).
+    conv_state [B, d_inner + 2N, k-1] (the last k-1 conv inputs, oldest first) and ssm_state
+    [B, H, P, N] carry a sequence across calls (None: zeros); the new ones are returned."""
     x = np.asarray(x, F64)
     bsz, length, d_m = x.shape
     n_tok = bsz * length
@@ -94,13 +96,13 @@ def rom_mamba2_forward(x, w: Dict[str, Optional[np.ndarray]], top_k: int, gate_m
     z = zxbcdt[:, :d_e]
     xbc_pre = zxbcdt[:, d_e:2 * d_e + 2 * n_state].reshape(bsz, length, d_e + 2 * n_state)
     dt_raw = zxbcdt[:, 2 * d_e + 2 * n_state:]
-    xbc, _ = causal_conv_silu(xbc_pre, w["conv_w"], w.get("conv_b"))
+    xbc, conv_out = causal_conv_silu(xbc_pre, w["conv_w"], w.get("conv_b"), conv_state)
     xs = xbc[:, :, :d_e].reshape(bsz, length, n_heads, headdim)
     b_mat = xbc[:, :, d_e:d_e + n_state]
     c_mat = xbc[:, :, d_e + n_state:]
     dt = softplus(dt_raw + np.asarray(w["dt_bias"], F64)[None, :]).reshape(bsz, length, n_heads)
     a = -np.exp(np.asarray(w["A_log"], F64))
-    y, state = ssd_scan(xs, dt, a, b_mat, c_mat, w["D"])
+    y, state = ssd_scan(xs, dt, a, b_mat, c_mat, w["D"], ssm_state)
     y = y.reshape(n_tok, d_e)
     g = gated_rms_norm(y, z, w["norm_w"], eps)
     out = np.zeros((n_tok, d_m), F64)
@@ -110,5 +112,13 @@ def rom_mamba2_forward(x, w: Dict[str, Optional[np.ndarray]], top_k: int, gate_m
         "logits": logits, "expert_idx": idx, "gate": gate, "counts": counts, "offsets": offsets,
         "perm": perm, "inv_perm": inv_perm, "zxbcdt": zxbcdt, "xbc": xbc.reshape(n_tok, -1),
         "dt": dt.reshape(n_tok, n_heads), "y": y, "g": g, "out": out.reshape(bsz, length, d_m),
-        "ssm_state": state,
+        "conv_state": conv_out, "ssm_state": state,
     }
+
+
+def rom_mamba2_step(x, w, top_k, gate_mode, headdim, conv_state, ssm_state, eps=1e-5, expert_idx=None):
+    """One new token per sequence: x [B, d_model]; the same dict with out [B, d_model] and the updated states."""
+    res = rom_mamba2_forward(np.asarray(x, F64)[:, None, :], w, top_k, gate_mode, headdim, eps, expert_idx,
+                             conv_state, ssm_state)
+    res["out"] = res["out"][:, 0, :]
+    return res

@@ -135,7 +135,10 @@ def load_library() -> ctypes.CDLL:
                                                 ctypes.POINTER(_RomMamba2WsLayout)]
     lib.rom_mamba2_forward.restype = ctypes.c_int
     lib.rom_mamba2_forward.argtypes = [ctypes.POINTER(RomMamba2Dims), ctypes.POINTER(_RomMamba2Weights), P, I64, I64,
-                                       F32, P, P, SZ, P]
+                                       F32, P, P, P, P, P, P, SZ, P]
+    lib.rom_mamba2_step.restype = ctypes.c_int
+    lib.rom_mamba2_step.argtypes = [ctypes.POINTER(RomMamba2Dims), ctypes.POINTER(_RomMamba2Weights), P, I64, F32, P, P,
+                                    P, P, SZ, P]
     lib.rom_strerror.restype = ctypes.c_char_p
     lib.rom_strerror.argtypes = [ctypes.c_int]
     lib.rom_profile_enable.restype = ctypes.c_int
@@ -342,14 +345,27 @@ def rom_mamba2_workspace_layout(dims: RomMamba2Dims, B: int, L: int) -> Dict[str
     return {n: int(getattr(lay, n)) for n, _ in _RomMamba2WsLayout._fields_}
 
 
-def rom_mamba2_forward(dims, weights, x, B, L, eps, out, ws):
-    ws_struct = _RomMamba2Weights()
+def _mamba2_weights_struct(weights) -> _RomMamba2Weights:
+    s = _RomMamba2Weights()
     for name, _ in _RomMamba2Weights._fields_:
-        setattr(ws_struct, name, _ptr(weights.get(name)))
+        setattr(s, name, _ptr(weights.get(name)))
+    return s
+
+
+def rom_mamba2_forward(dims, weights, x, B, L, eps, conv_state_in, ssm_state_in, out, conv_state_out, ssm_state_out,
+                       ws):
     code = load_library().rom_mamba2_forward(
-        ctypes.byref(dims), ctypes.byref(ws_struct), _ptr(x), B, L, eps, _ptr(out), _ptr(ws),
+        ctypes.byref(dims), ctypes.byref(_mamba2_weights_struct(weights)), _ptr(x), B, L, eps, _ptr(conv_state_in),
+        _ptr(ssm_state_in), _ptr(out), _ptr(conv_state_out), _ptr(ssm_state_out), _ptr(ws),
         ws.numel() * ws.element_size() if ws is not None else 0, _stream())
     _check(code, "rom_mamba2_forward")
+
+
+def rom_mamba2_step(dims, weights, x, B, eps, conv_state, ssm_state, out, ws):
+    code = load_library().rom_mamba2_step(
+        ctypes.byref(dims), ctypes.byref(_mamba2_weights_struct(weights)), _ptr(x), B, eps, _ptr(conv_state),
+        _ptr(ssm_state), _ptr(out), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check(code, "rom_mamba2_step")
 
 
 def rom_profile_enable(max_calls: int) -> None:
@@ -759,8 +775,25 @@ class RomMamba2Layer:
         off = lay[name]
         return self._ws[off:off + nbytes].view(dtype).view(shape)
 
-    def forward(self, x: torch.Tensor) -> torch.Tensor:
+    def state_shapes(self, B: int):
+        d = self.dims
+        return (B, d.d_inner + 2 * d.d_state, d.d_conv - 1), (B, d.d_inner // d.headdim, d.d_state, d.headdim)
+
+    def forward(self, x: torch.Tensor, conv_state=None, ssm_state=None, return_states=False):
         B, L = int(x.shape[0]), int(x.shape[1])
         out = torch.empty_like(x)
-        rom_mamba2_forward(self.dims, self.weights, x, B, L, self.eps, out, self.workspace(max(B, 1), max(L, 1)))
+        conv_out = ssm_out = None
+        if return_states:
+            cs, ss = self.state_shapes(B)
+            conv_out = torch.empty(cs, dtype=torch.float32, device=self.device)
+            ssm_out = torch.empty(ss, dtype=torch.float32, device=self.device)
+        rom_mamba2_forward(self.dims, self.weights, x, B, L, self.eps, conv_state, ssm_state, out, conv_out, ssm_out,
+                           self.workspace(max(B, 1), max(L, 1)))
+        return (out, conv_out, ssm_out) if return_states else out
+
+    def step(self, x: torch.Tensor, conv_state: torch.Tensor, ssm_state: torch.Tensor, out=None) -> torch.Tensor:
+        """x [B, d_model]; the states are updated in place."""
+        B = int(x.shape[0])
+        out = torch.empty_like(x) if out is None else out
+        rom_mamba2_step(self.dims, self.weights, x, B, self.eps, conv_state, ssm_state, out, self.workspace(max(B, 1), 1))
         return out

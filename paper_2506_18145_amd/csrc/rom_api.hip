@@ -857,7 +857,7 @@ namespace {
 struct Mamba2Plan {           // byte offsets inside the workspace
   size_t total;
   size_t expert_idx, gate, counts, offsets, perm, inv_perm, tok_of_pos, block_counts, logits;
-  size_t zxbcdt, zx_sorted, xbc, yz, g, op_sorted, carry;
+  size_t zxbcdt, zx_sorted, xbc, yz, g, op_sorted, carry, conv_tmp;
 };
 
 int check_mamba2_dims(const rom_mamba2_dims *d) {
@@ -900,6 +900,8 @@ Mamba2Plan make_mamba2_plan(const rom_mamba2_dims *d, int64_t n_seq, int64_t seq
   p.g = take(N * De * 2);
   p.op_sorted = K > 1 ? take(S * Dm * 2) : kNone;
   p.carry = take(ssd_carry_bytes(n_seq, seq_len, static_cast<int>(H), d->d_state));
+  // the conv writes its end state beside the old one when a sequence is cut into runs
+  p.conv_tmp = take(seq_len > kConvInPlaceMaxLen ? static_cast<size_t>(n_seq) * Dc * 3 * 4 : 0);
   p.total = off;
   return p;
 }
@@ -931,7 +933,8 @@ int rom_mamba2_workspace_layout(const rom_mamba2_dims *dims, int64_t B, int64_t 
 }
 
 int rom_mamba2_forward(const rom_mamba2_dims *d, const rom_mamba2_weights *w, const void *x, int64_t B, int64_t L,
-                       float eps, void *out, void *ws, size_t ws_bytes, void *hip_stream) {
+                       float eps, const float *conv_in, const float *ssm_in, void *out, float *conv_out, float *ssm_out,
+                       void *ws, size_t ws_bytes, void *hip_stream) {
   int rc = check_mamba2_dims(d);
   if (rc != ROM_OK) return rc;
   if (!w) return ROM_E_INVAL;
@@ -946,6 +949,14 @@ int rom_mamba2_forward(const rom_mamba2_dims *d, const rom_mamba2_weights *w, co
   if (!x || !out || !ws || x == out) return ROM_E_INVAL;
   if (!aligned16(x) || !aligned16(out) || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return ROM_E_INVAL;
   if (B * L * d->top_k > (1ll << 30) || B > 65535) return ROM_E_UNSUPPORTED;
+  {
+    const float *states[] = {conv_in, ssm_in, conv_out, ssm_out};
+    for (const float *ptr : states)
+      if (ptr && !aligned16(ptr)) return ROM_E_INVAL;
+    // a sequence longer than one conv run / one chunk is worked on by several workgroups: they would
+    // read the old state while another writes the new one
+    if (L > kConvInPlaceMaxLen && ((conv_in && conv_in == conv_out) || (ssm_in && ssm_in == ssm_out))) return ROM_E_INVAL;
+  }
   const int64_t N = B * L;
   const Mamba2Plan p = make_mamba2_plan(d, B, L);
   if (ws_bytes < p.total) return ROM_E_WORKSPACE;
@@ -993,14 +1004,24 @@ int rom_mamba2_forward(const rom_mamba2_dims *d, const rom_mamba2_weights *w, co
 
   // short conv + SiLU over the channels x | B | C
   mark.begin(ROM_STAGE_CONV, s);
-  ROM_TRY(launch_conv_silu(d->dtype, at(p.zxbcdt) + static_cast<size_t>(De) * 2, Dp, w->conv_w, w->conv_b, nullptr,
-                           nullptr, at(p.xbc), B, L, Dc, s));
+  {
+    float *ctmp = reinterpret_cast<float *>(at(p.conv_tmp));
+    const bool beside = conv_out && L > kConvInPlaceMaxLen;
+    ROM_TRY(launch_conv_silu(d->dtype, at(p.zxbcdt) + static_cast<size_t>(De) * 2, Dp, w->conv_w, w->conv_b, conv_in,
+                             beside ? ctmp : conv_out, at(p.xbc), B, L, Dc, s));
+    if (beside) {
+      const int64_t n = B * Dc * 3;
+      hipLaunchKernelGGL(copy_f32_kernel, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, s, ctmp, conv_out, n);
+      ROM_TRY(hipGetLastError());
+    }
+  }
   mark.end(ROM_STAGE_CONV, s);
 
   // recurrence, D skip, SiLU(z) gate
   mark.begin(ROM_STAGE_SCAN, s);
   ROM_TRY(launch_ssd_scan(at(p.xbc), Dc, 0, De, De + Ns, at(p.zxbcdt), Dp, 2 * De + 2 * Ns, at(p.zxbcdt), Dp, w->dt_bias,
-                          w->A_log, w->D, B, L, H, Ns, reinterpret_cast<float *>(at(p.carry)), at(p.yz), De, s));
+                          w->A_log, w->D, ssm_in, ssm_out, B, L, H, Ns, reinterpret_cast<float *>(at(p.carry)), at(p.yz), De,
+                          s));
   mark.end(ROM_STAGE_SCAN, s);
 
   // RMS norm of the gated rows
@@ -1028,6 +1049,13 @@ int rom_mamba2_forward(const rom_mamba2_dims *d, const rom_mamba2_weights *w, co
     mark.end(ROM_STAGE_OUT_PROJ, s);
   }
   return ROM_OK;
+}
+
+int rom_mamba2_step(const rom_mamba2_dims *d, const rom_mamba2_weights *w, const void *x, int64_t B, float eps,
+                    float *conv_state, float *ssm_state, void *out, void *ws, size_t ws_bytes, void *hip_stream) {
+  if (B > 0 && (!conv_state || !ssm_state)) return ROM_E_INVAL;
+  return rom_mamba2_forward(d, w, x, B, 1, eps, conv_state, ssm_state, out, conv_state, ssm_state, ws, ws_bytes,
+                            hip_stream);
 }
 
 size_t rom_backward_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L) {

@@ -169,13 +169,15 @@ hipError_t launch_wgrad(int dtype, const void *A, int64_t lda, int M, const void
 //   xbc bf16 [B*L, ld_xbc] holds x (head h at columns x_col + 64 h), B (b_col .. + d_state) and C (c_col ..)
 //   after conv + SiLU; dt_raw bf16 [B*L, ld_dt], column dt_col + h, before bias and softplus; z bf16
 //   [B*L, ld_z], head h at columns 64 h; dt_bias, A_log, D f32 [n_heads]; yz bf16 [B*L, ld_y] =
-//   (y + D x) * SiLU(z); carry: f32 scratch of ssd_carry_bytes()
+//   (y + D x) * SiLU(z); h_in / h_out f32 [B, n_heads, d_state, 64] or NULL: the state before the first
+//   and after the last step (they may be the same buffer only for L <= 64: one chunk, one segment);
+//   carry: f32 scratch of ssd_carry_bytes()
 bool ssd_supported(int d_state, int headdim);
 size_t ssd_carry_bytes(int64_t B, int64_t L, int n_heads, int d_state);
 hipError_t launch_ssd_scan(const void *xbc, int64_t ld_xbc, int x_col, int b_col, int c_col, const void *dt_raw,
                            int64_t ld_dt, int dt_col, const void *z, int64_t ld_z, const float *dt_bias,
-                           const float *A_log, const float *D, int64_t B, int64_t L, int n_heads, int d_state,
-                           float *carry, void *yz, int64_t ld_y, hipStream_t s);
+                           const float *A_log, const float *D, const float *h_in, float *h_out, int64_t B, int64_t L,
+                           int n_heads, int d_state, float *carry, void *yz, int64_t ld_y, hipStream_t s);
 // out[n, :] = in[n, :] / sqrt(mean(in[n, :]^2) + eps) * w  (bf16 rows of n_cols, n_cols % 8 == 0; out may be in)
 hipError_t launch_rms_rows(const void *in, const float *w, float eps, int64_t n_rows, int n_cols, void *out,
                            hipStream_t s);

@@ -114,6 +114,7 @@ __device__ __forceinline__ bf16x8_t frag_from_halves(const u32x2_t &lo, const u3
 //   xbc   bf16 [B*L, ld_xbc]: x of head h at columns x_col + 64 h, B at b_col, C at c_col (after conv + SiLU)
 //   dt_raw bf16 [B*L, ld_dt]: column dt_col + h, before bias and softplus;   z bf16 [B*L, ld_z]: column 64 h
 //   carry_state f32 [B][n_seg][H][NS][64], carry_decay f32 [B][n_seg][H]
+//   h_in / h_out f32 [B][H][NS][64] or NULL: the state before the first and after the last step
 //   yz    bf16 [B*L, ld_y]: (y + D x) * SiLU(z)
 template <int NS, bool CARRY>
 __global__ __launch_bounds__(256, 2) void ssd_kernel(const bf16_t *__restrict__ xbc, int64_t ld_xbc, int x_col, int b_col,
@@ -122,7 +123,8 @@ __global__ __launch_bounds__(256, 2) void ssd_kernel(const bf16_t *__restrict__ 
                                                   const float *__restrict__ dt_bias, const float *__restrict__ A_log,
                                                   const float *__restrict__ Dp, int64_t L, int n_seg, int64_t seg_len,
                                                   float *__restrict__ carry_state, float *__restrict__ carry_decay,
-                                                  bf16_t *__restrict__ yz, int64_t ld_y) {
+                                                  const float *h_in, float *h_out, bf16_t *__restrict__ yz,
+                                                  int64_t ld_y) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   SsdSmem<NS> &sm = *reinterpret_cast<SsdSmem<NS> *>(smem_raw);
   constexpr int kNB = NS / 16;          // 16-row blocks of the state
@@ -147,6 +149,13 @@ __global__ __launch_bounds__(256, 2) void ssd_kernel(const bf16_t *__restrict__ 
   for (int nb = 0; nb < kNB; ++nb) hacc[nb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
   const int64_t carry_stride = static_cast<int64_t>(NS) * kP;
   if (!CARRY) {
+    if (h_in) {
+      const float *sp = h_in + (b * n_heads + h) * carry_stride + wave * 16 + c;
+#pragma unroll
+      for (int nb = 0; nb < kNB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) hacc[nb][r] = sp[(16 * nb + 4 * g + r) * kP];
+    }
     // fold the earlier segments' (decay, end state from zero) in order
     for (int j = 0; j < seg; ++j) {
       const int64_t unit = (b * n_seg + j) * n_heads + h;
@@ -415,6 +424,47 @@ __global__ __launch_bounds__(256, 2) void ssd_kernel(const bf16_t *__restrict__ 
 #pragma unroll
       for (int r = 0; r < 4; ++r) sp[(16 * nb + 4 * g + r) * kP] = hacc[nb][r];
     if (tid == 0) carry_decay[unit] = log_decay_total;
+  } else if (h_out && seg == n_seg - 1) {
+    float *sp = h_out + (b * n_heads + h) * carry_stride + wave * 16 + c;
+#pragma unroll
+    for (int nb = 0; nb < kNB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) sp[(16 * nb + 4 * g + r) * kP] = hacc[nb][r];
+  }
+}
+
+// One step per sequence (L == 1): grid (n_heads, B); thread = (channel p, quarter of the states).
+// The state is read and written once, 64 consecutive channels per state index.
+template <int NS>
+__global__ __launch_bounds__(256) void ssd_step_kernel(const bf16_t *__restrict__ xbc, int64_t ld_xbc, int x_col, int b_col,
+                                                       int c_col, const bf16_t *__restrict__ dt_raw, int64_t ld_dt,
+                                                       int dt_col, const bf16_t *__restrict__ z, int64_t ld_z,
+                                                       const float *__restrict__ dt_bias, const float *__restrict__ A_log,
+                                                       const float *__restrict__ Dp, const float *h_in, float *h_out,
+                                                       bf16_t *__restrict__ yz, int64_t ld_y) {
+  __shared__ float part[4][kP];
+  const int tid = threadIdx.x, p = tid & 63, q = tid >> 6;
+  const int h = blockIdx.x, n_heads = gridDim.x;
+  const int64_t b = blockIdx.y;
+  const float dt = softplus_f32(bf16_to_f32(dt_raw[b * ld_dt + dt_col + h]) + dt_bias[h]);
+  const float dec = fast_exp2(-__expf(A_log[h]) * dt * kLog2e);
+  const bf16_t *row = xbc + b * ld_xbc;
+  const float xv = bf16_to_f32(row[x_col + h * kP + p]);
+  const float dtx = dt * xv;
+  const int64_t base = (b * n_heads + h) * static_cast<int64_t>(NS) * kP + p;
+  float acc = 0.0f;
+#pragma unroll 8
+  for (int j = 0; j < NS / 4; ++j) {
+    const int n = q * (NS / 4) + j;
+    const float hv = fmaf(dec, h_in ? h_in[base + static_cast<int64_t>(n) * kP] : 0.0f, dtx * bf16_to_f32(row[b_col + n]));
+    if (h_out) h_out[base + static_cast<int64_t>(n) * kP] = hv;
+    acc = fmaf(bf16_to_f32(row[c_col + n]), hv, acc);
+  }
+  part[q][p] = acc;
+  __syncthreads();
+  if (q == 0) {
+    const float y = part[0][p] + part[1][p] + part[2][p] + part[3][p] + Dp[h] * xv;
+    yz[b * ld_y + h * kP + p] = f32_to_bf16(y * silu_f32(bf16_to_f32(z[b * ld_z + h * kP + p])));
   }
 }
 
@@ -489,8 +539,14 @@ hipError_t ssd_allow_lds() {
 template <int NS>
 hipError_t ssd_dispatch(const bf16_t *xbc, int64_t ld_xbc, int x_col, int b_col, int c_col, const bf16_t *dt_raw,
                         int64_t ld_dt, int dt_col, const bf16_t *z, int64_t ld_z, const float *dt_bias,
-                        const float *A_log, const float *D, int64_t B, int64_t L, int n_heads, float *carry,
-                        bf16_t *yz, int64_t ld_y, hipStream_t s) {
+                        const float *A_log, const float *D, const float *h_in, float *h_out, int64_t B, int64_t L,
+                        int n_heads, float *carry, bf16_t *yz, int64_t ld_y, hipStream_t s) {
+  if (L == 1) {
+    hipLaunchKernelGGL((ssd_step_kernel<NS>), dim3(static_cast<unsigned>(n_heads), static_cast<unsigned>(B)), dim3(256), 0,
+                       s, xbc, ld_xbc, x_col, b_col, c_col, dt_raw, ld_dt, dt_col, z, ld_z, dt_bias, A_log, D, h_in, h_out,
+                       yz, ld_y);
+    return hipGetLastError();
+  }
   const SsdPlan p = ssd_plan(B, L, n_heads);
   float *carry_state = carry;
   float *carry_decay = carry + static_cast<size_t>(B) * p.n_seg * n_heads * NS * kP;
@@ -500,12 +556,14 @@ hipError_t ssd_dispatch(const bf16_t *xbc, int64_t ld_xbc, int x_col, int b_col,
   if (p.n_seg > 1) {
     if ((e = ssd_allow_lds<NS, true>()) != hipSuccess) return e;
     hipLaunchKernelGGL((ssd_kernel<NS, true>), grid, dim3(256), lds, s, xbc, ld_xbc, x_col, b_col, c_col, dt_raw, ld_dt,
-                       dt_col, z, ld_z, dt_bias, A_log, D, L, p.n_seg, p.seg_len, carry_state, carry_decay, yz, ld_y);
+                       dt_col, z, ld_z, dt_bias, A_log, D, L, p.n_seg, p.seg_len, carry_state, carry_decay, h_in, h_out, yz,
+                       ld_y);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if ((e = ssd_allow_lds<NS, false>()) != hipSuccess) return e;
   hipLaunchKernelGGL((ssd_kernel<NS, false>), grid, dim3(256), lds, s, xbc, ld_xbc, x_col, b_col, c_col, dt_raw, ld_dt,
-                     dt_col, z, ld_z, dt_bias, A_log, D, L, p.n_seg, p.seg_len, carry_state, carry_decay, yz, ld_y);
+                     dt_col, z, ld_z, dt_bias, A_log, D, L, p.n_seg, p.seg_len, carry_state, carry_decay, h_in, h_out, yz,
+                     ld_y);
   return hipGetLastError();
 }
 
@@ -521,18 +579,18 @@ bool ssd_supported(int d_state, int headdim) { return headdim == kP && (d_state 
 
 hipError_t launch_ssd_scan(const void *xbc, int64_t ld_xbc, int x_col, int b_col, int c_col, const void *dt_raw,
                            int64_t ld_dt, int dt_col, const void *z, int64_t ld_z, const float *dt_bias,
-                           const float *A_log, const float *D, int64_t B, int64_t L, int n_heads, int d_state,
-                           float *carry, void *yz, int64_t ld_y, hipStream_t s) {
+                           const float *A_log, const float *D, const float *h_in, float *h_out, int64_t B, int64_t L,
+                           int n_heads, int d_state, float *carry, void *yz, int64_t ld_y, hipStream_t s) {
   if (B * L <= 0) return hipSuccess;
   if (B * ssd_plan(B, L, n_heads).n_seg > 65535) return hipErrorInvalidValue;
   const bf16_t *xp = static_cast<const bf16_t *>(xbc), *dp = static_cast<const bf16_t *>(dt_raw);
   const bf16_t *zp = static_cast<const bf16_t *>(z);
   if (d_state == 128)
-    return ssd_dispatch<128>(xp, ld_xbc, x_col, b_col, c_col, dp, ld_dt, dt_col, zp, ld_z, dt_bias, A_log, D, B, L, n_heads,
-                             carry, static_cast<bf16_t *>(yz), ld_y, s);
+    return ssd_dispatch<128>(xp, ld_xbc, x_col, b_col, c_col, dp, ld_dt, dt_col, zp, ld_z, dt_bias, A_log, D, h_in, h_out, B,
+                             L, n_heads, carry, static_cast<bf16_t *>(yz), ld_y, s);
   if (d_state == 64)
-    return ssd_dispatch<64>(xp, ld_xbc, x_col, b_col, c_col, dp, ld_dt, dt_col, zp, ld_z, dt_bias, A_log, D, B, L, n_heads,
-                            carry, static_cast<bf16_t *>(yz), ld_y, s);
+    return ssd_dispatch<64>(xp, ld_xbc, x_col, b_col, c_col, dp, ld_dt, dt_col, zp, ld_z, dt_bias, A_log, D, h_in, h_out, B,
+                            L, n_heads, carry, static_cast<bf16_t *>(yz), ld_y, s);
   return hipErrorInvalidValue;
 }
 

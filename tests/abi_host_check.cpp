@@ -165,14 +165,21 @@ int main() {
     CHECK(rom_mamba2_workspace_layout(&bad, 1, 64, &lay) == ROM_E_UNSUPPORTED);
     rom_mamba2_weights mw;
     std::memset(&mw, 0, sizeof(mw));
-    CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, 1e-5f, addr + 4096, addr, 4096, nullptr) == ROM_E_INVAL);   // NULL weights
+    CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);   // NULL weights
     mw.w_router = addr; mw.w_in = addr; mw.conv_w = reinterpret_cast<const float *>(addr);
     mw.dt_bias = mw.A_log = mw.D = mw.norm_w = reinterpret_cast<const float *>(addr); mw.w_out = addr;
-    CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, 1e-5f, addr + 4096, addr, 4096, nullptr) == ROM_E_WORKSPACE);
-    CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, -1.0f, addr + 4096, addr, 4096, nullptr) == ROM_E_INVAL);
-    CHECK(rom_mamba2_forward(&m, &mw, addr, 0, 64, 1e-5f, addr + 4096, addr, 4096, nullptr) == ROM_OK);
-    CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, 1e-5f, addr, addr, 4096, nullptr) == ROM_E_INVAL);          // out == x
-    CHECK(rom_mamba2_forward(nullptr, &mw, addr, 1, 64, 1e-5f, addr + 4096, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+    {
+      float *st = reinterpret_cast<float *>(addr);
+      CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, 1e-5f, st, nullptr, addr + 4096, st, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);   // in-place state on a long sequence
+      CHECK(rom_mamba2_step(&m, &mw, addr, 4, 1e-5f, nullptr, st, addr + 4096, addr, 4096, nullptr) == ROM_E_INVAL);
+      CHECK(rom_mamba2_step(&m, &mw, addr, 4, 1e-5f, st, st, addr + 4096, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+      CHECK(rom_mamba2_step(&m, &mw, addr, 0, 1e-5f, nullptr, nullptr, addr + 4096, addr, 4096, nullptr) == ROM_OK);
+    }
+    CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, -1.0f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_mamba2_forward(&m, &mw, addr, 0, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_OK);
+    CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, 1e-5f, nullptr, nullptr, addr, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);          // out == x
+    CHECK(rom_mamba2_forward(nullptr, &mw, addr, 1, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
   }
 
   // ---- strings and the profiling bookkeeping

@@ -129,8 +129,113 @@ def test_mamba2_argument_checks():
     out = torch.empty_like(x)
     small = torch.empty(1024, dtype=torch.uint8, device=x.device)
     with pytest.raises(RomError):
-        rom_mamba2_forward(layer.dims, layer.weights, x, 2, 200, EPS, out, small)
+        rom_mamba2_forward(layer.dims, layer.weights, x, 2, 200, EPS, None, None, out, None, None, small)
     bad = RomMamba2Dims(256, 512, 32, 4, 64, 4, 1, 1, 0)                 # state size 32: unsupported
     assert rom_mamba2_workspace_bytes(bad, 1, 64) == 0
     # an empty batch is a no-op
-    rom_mamba2_forward(layer.dims, layer.weights, x[:0].contiguous(), 0, 200, EPS, out[:0].contiguous(), small)
+    rom_mamba2_forward(layer.dims, layer.weights, x[:0].contiguous(), 0, 200, EPS, None, None, out[:0].contiguous(), None,
+                       None, small)
+    # a long sequence may not update its states in place
+    cs_shape, ss_shape = layer.state_shapes(2)
+    cs = torch.zeros(cs_shape, device=x.device)
+    ss = torch.zeros(ss_shape, device=x.device)
+    with pytest.raises(RomError):
+        rom_mamba2_forward(layer.dims, layer.weights, x, 2, 200, EPS, cs, ss, out, cs, ss, layer.workspace(2, 200))
+
+
+def _oracle_states(ref):
+    """The oracle's states in the library's layouts: conv [B, channels, 3]; H [B, heads, N, P]."""
+    return ref["conv_state"], ref["ssm_state"].transpose(0, 1, 3, 2)
+
+
+@pytest.mark.parametrize("name,overrides", [
+    ("m2_small", dict(cfg_id=40)),                       # one segment
+    ("m2_mid", dict(batch=1, seq_len=1100, cfg_id=41)),   # segments: the carried state enters the fold
+])
+def test_mamba2_states_in_and_out(name, overrides):
+    """A call that starts from given states and returns the new ones, against the oracle; and a
+    sequence fed in two calls gives the output of one call up to the rounding of the carried state."""
+    cfg = get_mamba2_config(name, **overrides)
+    w_np, x_np = make_mamba2_weights(cfg), make_mamba2_input(cfg)
+    rng = np.random.default_rng(cfg.cfg_id)
+    cs_np = rng.standard_normal((cfg.batch, cfg.d_conv_ch, 3)).astype(np.float32)
+    ss_np = rng.standard_normal((cfg.batch, cfg.n_heads, cfg.d_state, cfg.headdim)).astype(np.float32)
+    layer = RomMamba2Layer(cfg, w_np, eps=EPS)
+    x = layer.to_device(x_np)
+    cs, ss = torch.from_numpy(cs_np).cuda(), torch.from_numpy(ss_np).cuda()
+    out, cs_out, ss_out = layer.forward(x, cs, ss, return_states=True)
+    torch.cuda.synchronize()
+    idx = to_np(layer.ws_view("expert_idx", cfg.batch, cfg.seq_len))
+    ref = M.rom_mamba2_forward(x_np, w_np, cfg.top_k, cfg.gate_mode, cfg.headdim, EPS, expert_idx=idx,
+                               conv_state=cs_np, ssm_state=ss_np.transpose(0, 1, 3, 2))
+    cs_ref, ss_ref = _oracle_states(ref)
+    errs = {"out": rel_err(to_np(out), ref["out"]), "conv_state": rel_err(to_np(cs_out), cs_ref),
+            "ssm_state": rel_err(to_np(ss_out), ss_ref)}
+    print(f"[{cfg.name} states] " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    assert all(v <= TOL["bf16"] for v in errs.values()), errs
+    # the same sequence in two calls
+    cut = cfg.seq_len // 2 + 3
+    o1, c1, s1 = layer.forward(x[:, :cut].contiguous(), cs, ss, return_states=True)
+    o2, c2, s2 = layer.forward(x[:, cut:].contiguous(), c1, s1, return_states=True)
+    torch.cuda.synchronize()
+    both = torch.cat([o1, o2], dim=1)
+    assert rel_err(to_np(both), to_np(out)) <= 1e-2
+    assert rel_err(to_np(c2), to_np(cs_out)) <= 1e-2      # (another tile shape may add a row's products in another order)
+    assert rel_err(to_np(s2), to_np(ss_out)) <= 1e-2
+
+
+def test_mamba2_step_decodes_like_the_oracle():
+    """64 consecutive steps of 5 sequences through rom_mamba2_step (states in place), every step's
+    output and the final states against the oracle's step."""
+    cfg = get_mamba2_config("m2_mid", batch=5, seq_len=64, cfg_id=42)
+    w_np, x_np = make_mamba2_weights(cfg), make_mamba2_input(cfg)
+    layer = RomMamba2Layer(cfg, w_np, eps=EPS)
+    cs_shape, ss_shape = layer.state_shapes(cfg.batch)
+    cs = torch.zeros(cs_shape, device="cuda:0")
+    ss = torch.zeros(ss_shape, device="cuda:0")
+    cs_ref = np.zeros(cs_shape)
+    ss_ref = np.zeros((cfg.batch, cfg.n_heads, cfg.headdim, cfg.d_state))
+    worst = 0.0
+    for t in range(cfg.seq_len):
+        xt = layer.to_device(np.ascontiguousarray(x_np[:, t]))
+        out = layer.step(xt, cs, ss)
+        torch.cuda.synchronize()
+        idx = to_np(layer.ws_view("expert_idx", cfg.batch, 1))
+        ref = M.rom_mamba2_step(x_np[:, t], w_np, cfg.top_k, cfg.gate_mode, cfg.headdim, cs_ref, ss_ref, EPS, expert_idx=idx)
+        cs_ref, ss_ref = ref["conv_state"], ref["ssm_state"]
+        worst = max(worst, rel_err(to_np(out), ref["out"]))
+    errs = {"out (worst step)": worst, "conv_state": rel_err(to_np(cs), cs_ref),
+            "ssm_state": rel_err(to_np(ss), ss_ref.transpose(0, 1, 3, 2))}
+    print(f"[{cfg.name} step x{cfg.seq_len}] " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    assert all(v <= TOL["bf16"] for v in errs.values()), errs
+    # the step and the sequence form agree: the same tokens through one forward call
+    x = layer.to_device(x_np)
+    out_seq, cs_seq, ss_seq = layer.forward(x, return_states=True)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(ss_seq), to_np(ss)) <= 1e-2 and rel_err(to_np(cs_seq), to_np(cs)) <= 1e-6
+
+
+def test_mamba2_step_full_size():
+    """256 sequences at the 16K-context layer's size (d_model 2048, 64 heads, state size 128): four
+    steps against the oracle."""
+    cfg = get_mamba2_config("m2_cfg2", batch=256, seq_len=4, cfg_id=43)
+    w_np, x_np = make_mamba2_weights(cfg), make_mamba2_input(cfg)
+    layer = RomMamba2Layer(cfg, w_np, eps=EPS)
+    cs_shape, ss_shape = layer.state_shapes(cfg.batch)
+    rng = np.random.default_rng(43)
+    cs_ref = rng.standard_normal(cs_shape).astype(np.float32)
+    ss_lib = (0.1 * rng.standard_normal(ss_shape)).astype(np.float32)
+    cs, ss = torch.from_numpy(cs_ref).cuda(), torch.from_numpy(ss_lib).cuda()
+    cs_ref = cs_ref.astype(np.float64)
+    ss_ref = ss_lib.transpose(0, 1, 3, 2).astype(np.float64)
+    for t in range(cfg.seq_len):
+        out = layer.step(layer.to_device(np.ascontiguousarray(x_np[:, t])), cs, ss)
+        torch.cuda.synchronize()
+        idx = to_np(layer.ws_view("expert_idx", cfg.batch, 1))
+        ref = M.rom_mamba2_step(x_np[:, t], w_np, cfg.top_k, cfg.gate_mode, cfg.headdim, cs_ref, ss_ref, EPS, expert_idx=idx)
+        cs_ref, ss_ref = ref["conv_state"], ref["ssm_state"]
+        err = rel_err(to_np(out), ref["out"])
+        print(f"[m2_cfg2 step {t}] out={err:.2e}", flush=True)
+        assert err <= TOL["bf16"]
+    assert rel_err(to_np(ss), ss_ref.transpose(0, 1, 3, 2)) <= TOL["bf16"]
+    assert rel_err(to_np(cs), cs_ref) <= TOL["bf16"]

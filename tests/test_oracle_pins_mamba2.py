@@ -192,6 +192,31 @@ def test_layer_is_causal_and_sequences_are_independent():
     assert np.abs(moved[0, 6:] - base[0, 6:]).max() > 1e-3
 
 
+def test_layer_state_carry_and_step_equal_the_unsplit_run():
+    """A sequence fed in two calls, or token by token through the step, gives what one call gives:
+    pins the state arguments (conv history order, state layout) to the stateless layer."""
+    cfg = _tiny_cfg(top_k=2, gate_mode=1, seq_len=9)
+    w = S.make_mamba2_weights(cfg)
+    x = S.make_mamba2_input(cfg).astype(np.float64)
+    whole = M.rom_mamba2_forward(x, w, 2, 1, cfg.headdim)
+    first = M.rom_mamba2_forward(x[:, :4], w, 2, 1, cfg.headdim)
+    second = M.rom_mamba2_forward(x[:, 4:], w, 2, 1, cfg.headdim, conv_state=first["conv_state"],
+                                  ssm_state=first["ssm_state"])
+    np.testing.assert_allclose(np.concatenate([first["out"], second["out"]], axis=1), whole["out"], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(second["ssm_state"], whole["ssm_state"], rtol=1e-10, atol=1e-12)
+    np.testing.assert_array_equal(second["conv_state"], whole["conv_state"])
+    # the conv state is the last three inputs of the conv, oldest first
+    xbc_pre = whole["zxbcdt"][:, cfg.d_inner:2 * cfg.d_inner + 2 * cfg.d_state].reshape(cfg.batch, cfg.seq_len, -1)
+    np.testing.assert_array_equal(whole["conv_state"], xbc_pre[:, -3:, :].transpose(0, 2, 1))
+    cs = np.zeros((cfg.batch, cfg.d_conv_ch, cfg.d_conv - 1))
+    ss = np.zeros((cfg.batch, cfg.n_heads, cfg.headdim, cfg.d_state))
+    for t in range(cfg.seq_len):
+        res = M.rom_mamba2_step(x[:, t], w, 2, 1, cfg.headdim, cs, ss)
+        cs, ss = res["conv_state"], res["ssm_state"]
+        np.testing.assert_allclose(res["out"], whole["out"][:, t], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(ss, whole["ssm_state"], rtol=1e-10, atol=1e-12)
+
+
 def test_mamba2_synth_shapes():
     cfg = S.get_mamba2_config("m2_cfg2")
     assert (cfg.n_heads, cfg.d_in_proj, cfg.d_conv_ch) == (64, 8512, 4352)
