@@ -22,4 +22,9 @@ from .configs import (  # noqa: F401
     get_mamba2_config,
     make_mamba2_weights,
     make_mamba2_input,
+    GdnConfig,
+    GDN_CONFIGS,
+    get_gdn_config,
+    make_gdn_weights,
+    make_gdn_input,
 )

@@ -275,3 +275,94 @@ def make_mamba2_input(cfg: Mamba2Config) -> np.ndarray:
     if cfg.rms_norm_x:
         x /= np.sqrt(np.mean(np.square(x, dtype=np.float32), axis=-1, keepdims=True))
     return _store(cfg, x)
+
+
+# --------------------------------------------------------------------------
+# RoM on a Gated DeltaNet layer (Sec. 5.2, Table 3): shapes of the published layer at small scale
+# (value width 2 x d_model, key width d_model, conv width 4); the paper gives none of its own
+# --------------------------------------------------------------------------
+@dataclass(frozen=True)
+class GdnConfig:
+    name: str
+    cfg_id: int          # seed base = 1000 * cfg_id + tensor id
+    batch: int
+    seq_len: int
+    d_model: int
+    n_heads: int
+    d_k: int             # key / query channels per head
+    d_v: int             # value channels per head
+    n_experts: int
+    top_k: int
+    gate_mode: int
+    dtype: str = "bf16"
+    d_conv: int = 4
+    weight_std: float = 0.02
+    rms_norm_x: bool = False
+    router_bias: Optional[tuple] = None
+
+    @property
+    def d_kt(self) -> int:
+        return self.n_heads * self.d_k
+
+    @property
+    def d_vt(self) -> int:
+        return self.n_heads * self.d_v
+
+    @property
+    def n_tokens(self) -> int:
+        return self.batch * self.seq_len
+
+    @property
+    def d_in_proj(self) -> int:          # rows of one expert's input projection: z | q | k | v | b | a
+        return 2 * self.d_vt + 2 * self.d_kt + 2 * self.n_heads
+
+    @property
+    def d_conv_ch(self) -> int:          # channels the short conv runs over: q | k | v
+        return 2 * self.d_kt + self.d_vt
+
+
+GDN_CONFIGS: Dict[str, GdnConfig] = {
+    "gdn_small": GdnConfig("gdn_small", 50, 2, 200, 256, 8, 64, 64, 4, 1, 0),
+    "gdn_mid": GdnConfig("gdn_mid", 51, 2, 1500, 512, 16, 64, 64, 6, 2, 1),
+    # the headline layer's counterpart: 16K context, d_model 2048, 8 experts top-1
+    "gdn_cfg2": GdnConfig("gdn_cfg2", 52, 1, 16384, 2048, 32, 64, 128, 8, 1, 0,
+                          weight_std=0.02 / float(np.sqrt(2 * 48)), rms_norm_x=True),
+}
+
+
+def get_gdn_config(name: str, **overrides) -> GdnConfig:
+    cfg = GDN_CONFIGS[name]
+    return replace(cfg, **overrides) if overrides else cfg
+
+
+def make_gdn_weights(cfg: GdnConfig) -> Dict[str, Optional[np.ndarray]]:
+    """w_router [E, d_model], b_router, w_in [E, d_in_proj, d_model] (rows z | q | k | v | b | a),
+    conv_w [d_conv_ch, k], conv_b, dt_bias / A_log [H], norm_w [d_v], w_out [E, d_model, D_v];
+    float32, the bf16-stored ones exactly representable in bf16."""
+    E, Dm, H = cfg.n_experts, cfg.d_model, cfg.n_heads
+    w: Dict[str, Optional[np.ndarray]] = {}
+    w["w_router"] = _store(cfg, _normal(cfg, _T_WR, (E, Dm), 0.02))
+    w["b_router"] = (np.asarray(cfg.router_bias, dtype=np.float32) if cfg.router_bias is not None else None)
+    w_in = _normal(cfg, _T_WIN, (E, cfg.d_in_proj, Dm), cfg.weight_std)
+    # the two per-head logits are single numbers: at the projections' scale they would never leave
+    # the middle of the sigmoid / softplus, so their rows are drawn ten times wider
+    w_in[:, 2 * cfg.d_vt + 2 * cfg.d_kt:, :] *= 10.0
+    w["w_in"] = _store(cfg, w_in)
+    lim = 1.0 / np.sqrt(cfg.d_conv)
+    w["conv_w"] = _rng(cfg, _T_CW).uniform(-lim, lim, (cfg.d_conv_ch, cfg.d_conv)).astype(np.float32)
+    w["conv_b"] = _rng(cfg, _T_CB).uniform(-lim, lim, (cfg.d_conv_ch,)).astype(np.float32)
+    # per head: time step log-uniform in [1e-3, 1e-1] (dt_bias is its inverse softplus), decay rate uniform in [1, 16]
+    tau = np.exp(_rng(cfg, _T_DTB).uniform(np.log(1e-3), np.log(1e-1), (H,)))
+    w["dt_bias"] = (tau + np.log(-np.expm1(-tau))).astype(np.float32)
+    w["A_log"] = np.log(_rng(cfg, _T_WDT).uniform(1.0, 16.0, (H,))).astype(np.float32)
+    w["norm_w"] = _rng(cfg, _T_NORM).uniform(0.7, 1.3, (cfg.d_v,)).astype(np.float32)
+    w["w_out"] = _store(cfg, _normal(cfg, _T_WOUT, (E, Dm, cfg.d_vt), cfg.weight_std))
+    return w
+
+
+def make_gdn_input(cfg: GdnConfig) -> np.ndarray:
+    """x [B, L, d_model]."""
+    x = _normal(cfg, _T_X, (cfg.batch, cfg.seq_len, cfg.d_model), 1.0)
+    if cfg.rms_norm_x:
+        x /= np.sqrt(np.mean(np.square(x, dtype=np.float32), axis=-1, keepdims=True))
+    return _store(cfg, x)
