@@ -456,6 +456,84 @@ ROM_API int rom_mamba2_step(const rom_mamba2_dims *dims, const rom_mamba2_weight
                             int64_t B, float eps, float *conv_state, float *ssm_state, void *out,
                             void *ws, size_t ws_bytes, void *hip_stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * RoM on a Gated DeltaNet layer (Sec. 5.2, Table 3: every major projection of the block under the one
+ * shared router).  The paper prints no equations for this variant; what is computed (readings: the
+ * published Gated DeltaNet layer, routed the way Eq. (9)-(13) route the Mamba layer):
+ *
+ *   router      as in rom_layer_forward (Eq. (9))
+ *   in          p[n,:] = sum_k w_in[idx[n,k]] x[n,:]            (unweighted sum, as Eq. (10)/(11));
+ *               columns z [D_v] | q [D_k] | k [D_k] | v [D_v] | b [H] | a [H]   (D_k = H d_k, D_v = H d_v)
+ *   conv        q | k | v <- SiLU(conv_b + causal depthwise conv_4(q | k | v))
+ *   per head    q <- q / sqrt(sum q^2 + 1e-6) / sqrt(d_k),  k <- k / sqrt(sum k^2 + 1e-6),
+ *               beta = sigmoid(b),  g = -exp(A_log[h]) softplus(a + dt_bias[h]);
+ *               S <- exp(g) S;  u = beta (v - S k);  S <- S + u k^T;  o = S q       (S: d_v x d_k)
+ *   norm, gate  y = RMSNorm_head(o) * norm_w * SiLU(z)      (norm over each head's d_v channels)
+ *   out         out[n,:] = sum_k gate[n,k] * (w_out[idx[n,k]] y[n,:])              (as Eq. (12)/(13))
+ *
+ * Supported: ROM_DTYPE_BF16, d_v == 64, d_k in {64, 128}, d_conv == 4, n_heads % 4 == 0, d_model % 8
+ * == 0, 1 <= top_k <= n_experts <= 64, top_k <= 8.  Anything else: ROM_E_UNSUPPORTED / ROM_E_INVAL. */
+typedef struct rom_gdn_dims {
+  int32_t d_model;
+  int32_t n_heads;        /* H                                               */
+  int32_t d_k;            /* key / query channels per head                   */
+  int32_t d_v;            /* value channels per head                         */
+  int32_t d_conv;         /* 4                                               */
+  int32_t n_experts;
+  int32_t top_k;
+  int32_t dtype;          /* ROM_DTYPE_BF16                                  */
+  int32_t gate_mode;      /* as rom_dims                                     */
+} rom_gdn_dims;
+
+/* All pointers 16-byte aligned device pointers; "T" is bf16. */
+typedef struct rom_gdn_weights {
+  const void  *w_router;  /* T   [E, d_model]                                                   */
+  const float *b_router;  /* f32 [E] or NULL                                                    */
+  const void  *w_in;      /* T   [E, 2*D_v + 2*D_k + 2*H, d_model]; rows z | q | k | v | b | a  */
+  const float *conv_w;    /* f32 [2*D_k + D_v, 4] over the channels q | k | v                   */
+  const float *conv_b;    /* f32 [2*D_k + D_v] or NULL                                          */
+  const float *dt_bias;   /* f32 [H]                                                            */
+  const float *A_log;     /* f32 [H]                                                            */
+  const float *norm_w;    /* f32 [d_v]                                                          */
+  const void  *w_out;     /* T   [E, d_model, D_v]                                              */
+} rom_gdn_weights;
+
+/* Byte offsets of the intermediates inside the workspace after rom_gdn_forward. */
+typedef struct rom_gdn_ws_layout {
+  size_t total_bytes;
+  size_t expert_idx;   /* i32 [N*K]                                        */
+  size_t gate;         /* f32 [N*K]                                        */
+  size_t counts;       /* i32 [E]                                          */
+  size_t offsets;      /* i32 [E+1]                                        */
+  size_t perm;         /* i32 [N*K]                                        */
+  size_t inv_perm;     /* i32 [N*K]                                        */
+  size_t logits;       /* f32 [N, E]                                       */
+  size_t proj;         /* T   [N, 2*D_v + 2*D_k + 2*H]  (sum over k applied) */
+  size_t qkv;          /* T   [N, 2*D_k + D_v]  after conv + SiLU (not normalised) */
+  size_t y;            /* T   [N, D_v]  after norm and gate                */
+} rom_gdn_ws_layout;
+
+/* host-only; 0 / an error for invalid or unsupported dims */
+ROM_API size_t rom_gdn_workspace_bytes(const rom_gdn_dims *dims, int64_t B, int64_t L);
+ROM_API int rom_gdn_workspace_layout(const rom_gdn_dims *dims, int64_t B, int64_t L, rom_gdn_ws_layout *layout);
+
+/* The layer above on B sequences of L tokens.
+ *   x, out          T [B, L, d_model] (distinct);  eps: the head norm's epsilon (>= 0)
+ *   conv_state_in   f32 [B, 2*D_k + D_v, 3] or NULL (zeros): the conv's inputs at the three steps
+ *                   before the first, oldest first
+ *   ssm_state_in    f32 [B, H, d_k, d_v] or NULL (zeros): S^T before the first step
+ *   conv_state_out, ssm_state_out   the same after the last step, or NULL.  An output state may be the
+ *                   same buffer as its input only for L <= 32.
+ *   ws              rom_gdn_workspace_bytes(dims, B, L), 256-byte aligned
+ * One workgroup walks a (sequence, head) from its first step to its last: the call is parallel over
+ * B * H only.  Asynchronous on hip_stream, allocates nothing; B * L == 0 is a successful no-op; errors
+ * are reported before anything is launched.  With profiling on, the stages are recorded under
+ * ROM_STAGE_ROUTE, _PERMUTE, _IN_PROJ, _CONV, _SCAN (delta rule + norm + gate), _OUT_PROJ, _COMBINE. */
+ROM_API int rom_gdn_forward(const rom_gdn_dims *dims, const rom_gdn_weights *w, const void *x, int64_t B,
+                            int64_t L, float eps, const float *conv_state_in, const float *ssm_state_in,
+                            void *out, float *conv_state_out, float *ssm_state_out, void *ws,
+                            size_t ws_bytes, void *hip_stream);
+
 /* Static description of an error code. */
 ROM_API const char *rom_strerror(int code);
 

@@ -67,6 +67,21 @@ class _RomMamba2WsLayout(ctypes.Structure):
         "yz", "g")]
 
 
+class RomGdnDims(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "d_model", "n_heads", "d_k", "d_v", "d_conv", "n_experts", "top_k", "dtype", "gate_mode")]
+
+
+class _RomGdnWeights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in (
+        "w_router", "b_router", "w_in", "conv_w", "conv_b", "dt_bias", "A_log", "norm_w", "w_out")]
+
+
+class _RomGdnWsLayout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_size_t) for n in (
+        "total_bytes", "expert_idx", "gate", "counts", "offsets", "perm", "inv_perm", "logits", "proj", "qkv", "y")]
+
+
 def load_library() -> ctypes.CDLL:
     """Loads librom.so; raises if it has not been built (there is no fallback path)."""
     global _lib
@@ -139,6 +154,13 @@ def load_library() -> ctypes.CDLL:
     lib.rom_mamba2_step.restype = ctypes.c_int
     lib.rom_mamba2_step.argtypes = [ctypes.POINTER(RomMamba2Dims), ctypes.POINTER(_RomMamba2Weights), P, I64, F32, P, P,
                                     P, P, SZ, P]
+    lib.rom_gdn_workspace_bytes.restype = SZ
+    lib.rom_gdn_workspace_bytes.argtypes = [ctypes.POINTER(RomGdnDims), I64, I64]
+    lib.rom_gdn_workspace_layout.restype = ctypes.c_int
+    lib.rom_gdn_workspace_layout.argtypes = [ctypes.POINTER(RomGdnDims), I64, I64, ctypes.POINTER(_RomGdnWsLayout)]
+    lib.rom_gdn_forward.restype = ctypes.c_int
+    lib.rom_gdn_forward.argtypes = [ctypes.POINTER(RomGdnDims), ctypes.POINTER(_RomGdnWeights), P, I64, I64, F32, P, P,
+                                    P, P, P, P, SZ, P]
     lib.rom_strerror.restype = ctypes.c_char_p
     lib.rom_strerror.argtypes = [ctypes.c_int]
     lib.rom_profile_enable.restype = ctypes.c_int
@@ -366,6 +388,27 @@ def rom_mamba2_step(dims, weights, x, B, eps, conv_state, ssm_state, out, ws):
         ctypes.byref(dims), ctypes.byref(_mamba2_weights_struct(weights)), _ptr(x), B, eps, _ptr(conv_state),
         _ptr(ssm_state), _ptr(out), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
     _check(code, "rom_mamba2_step")
+
+
+def rom_gdn_workspace_bytes(dims: RomGdnDims, B: int, L: int) -> int:
+    return int(load_library().rom_gdn_workspace_bytes(ctypes.byref(dims), B, L))
+
+
+def rom_gdn_workspace_layout(dims: RomGdnDims, B: int, L: int) -> Dict[str, int]:
+    lay = _RomGdnWsLayout()
+    _check(load_library().rom_gdn_workspace_layout(ctypes.byref(dims), B, L, ctypes.byref(lay)), "rom_gdn_workspace_layout")
+    return {n: int(getattr(lay, n)) for n, _ in _RomGdnWsLayout._fields_}
+
+
+def rom_gdn_forward(dims, weights, x, B, L, eps, conv_state_in, ssm_state_in, out, conv_state_out, ssm_state_out, ws):
+    wstruct = _RomGdnWeights()
+    for name, _ in _RomGdnWeights._fields_:
+        setattr(wstruct, name, _ptr(weights.get(name)))
+    code = load_library().rom_gdn_forward(
+        ctypes.byref(dims), ctypes.byref(wstruct), _ptr(x), B, L, eps, _ptr(conv_state_in), _ptr(ssm_state_in), _ptr(out),
+        _ptr(conv_state_out), _ptr(ssm_state_out), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
+        _stream())
+    _check(code, "rom_gdn_forward")
 
 
 def rom_profile_enable(max_calls: int) -> None:
@@ -797,3 +840,78 @@ class RomMamba2Layer:
         out = torch.empty_like(x) if out is None else out
         rom_mamba2_step(self.dims, self.weights, x, B, self.eps, conv_state, ssm_state, out, self.workspace(max(B, 1), 1))
         return out
+
+
+class RomGdnLayer:
+    """Holds the parameters of one RoM-on-Gated-DeltaNet layer on the GPU plus a workspace, and forwards
+    to rom_gdn_forward."""
+
+    def __init__(self, cfg, weights_np, device="cuda:0", eps: float = 1e-5):
+        load_library()
+        if not torch.cuda.is_available():
+            raise RomError("RomGdnLayer needs a GPU: librom has no CPU path")
+        if cfg.dtype != "bf16":
+            raise RomError("rom_gdn_forward takes bf16 only")
+        self.device = torch.device(device)
+        self.tdtype = torch.bfloat16
+        self.eps = eps
+        self.dims = RomGdnDims(cfg.d_model, cfg.n_heads, cfg.d_k, cfg.d_v, cfg.d_conv, cfg.n_experts, cfg.top_k,
+                               ROM_DTYPE_BF16, cfg.gate_mode)
+        typed = {"w_router", "w_in", "w_out"}
+        self.weights: Dict[str, Optional[torch.Tensor]] = {}
+        for name, arr in weights_np.items():
+            if arr is None:
+                self.weights[name] = None
+                continue
+            t = arr if isinstance(arr, torch.Tensor) else torch.from_numpy(arr)
+            t = t.to(self.tdtype) if name in typed else t.to(torch.float32)
+            self.weights[name] = t.to(self.device).contiguous()
+        self._ws: Optional[torch.Tensor] = None
+
+    def to_device(self, arr) -> torch.Tensor:
+        return torch.from_numpy(arr).to(self.tdtype).to(self.device).contiguous()
+
+    def workspace(self, B: int, L: int) -> torch.Tensor:
+        need = rom_gdn_workspace_bytes(self.dims, B, L)
+        if need == 0:
+            raise RomError("rom_gdn_workspace_bytes returned 0: unsupported dims")
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def state_shapes(self, B: int):
+        d = self.dims
+        return (B, 2 * d.n_heads * d.d_k + d.n_heads * d.d_v, d.d_conv - 1), (B, d.n_heads, d.d_k, d.d_v)
+
+    def ws_view(self, name: str, B: int, L: int) -> torch.Tensor:
+        """Intermediate tensor `name` of the last forward call with these B, L."""
+        lay = rom_gdn_workspace_layout(self.dims, B, L)
+        d, n = self.dims, B * L
+        dk, dv = d.n_heads * d.d_k, d.n_heads * d.d_v
+        shapes = {
+            "expert_idx": (torch.int32, (n, d.top_k)), "gate": (torch.float32, (n, d.top_k)),
+            "counts": (torch.int32, (d.n_experts,)), "offsets": (torch.int32, (d.n_experts + 1,)),
+            "perm": (torch.int32, (n * d.top_k,)), "inv_perm": (torch.int32, (n * d.top_k,)),
+            "logits": (torch.float32, (n, d.n_experts)),
+            "proj": (self.tdtype, (n, 2 * dv + 2 * dk + 2 * d.n_heads)),
+            "qkv": (self.tdtype, (n, 2 * dk + dv)), "y": (self.tdtype, (n, dv)),
+        }
+        dtype, shape = shapes[name]
+        count = 1
+        for s in shape:
+            count *= s
+        nbytes = count * torch.empty((), dtype=dtype).element_size()
+        off = lay[name]
+        return self._ws[off:off + nbytes].view(dtype).view(shape)
+
+    def forward(self, x: torch.Tensor, conv_state=None, ssm_state=None, return_states=False):
+        B, L = int(x.shape[0]), int(x.shape[1])
+        out = torch.empty_like(x)
+        conv_out = ssm_out = None
+        if return_states:
+            cs, ss = self.state_shapes(B)
+            conv_out = torch.empty(cs, dtype=torch.float32, device=self.device)
+            ssm_out = torch.empty(ss, dtype=torch.float32, device=self.device)
+        rom_gdn_forward(self.dims, self.weights, x, B, L, self.eps, conv_state, ssm_state, out, conv_out, ssm_out,
+                        self.workspace(max(B, 1), max(L, 1)))
+        return (out, conv_out, ssm_out) if return_states else out

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 BUILD_DIR = os.path.join(ROOT, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "librom.so")
-SOURCES = ["rom_api.hip", "rom_route.hip", "rom_gemm.hip", "rom_seq.hip", "rom_bwd.hip", "rom_mamba2.hip"]
+SOURCES = ["rom_api.hip", "rom_route.hip", "rom_gemm.hip", "rom_seq.hip", "rom_bwd.hip", "rom_mamba2.hip", "rom_gdn.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -47,7 +47,7 @@ def build_library(verbose: bool = False) -> str:
         src, obj = pair
         return _run([hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
 
-    with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(7, len(SOURCES))) as pool:
         logs = list(pool.map(compile_one, zip(SOURCES, objs)))
     logs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]))
     if verbose:

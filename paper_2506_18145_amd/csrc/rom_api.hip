@@ -1058,6 +1058,191 @@ int rom_mamba2_step(const rom_mamba2_dims *d, const rom_mamba2_weights *w, const
                             hip_stream);
 }
 
+// ---------------------------------------------------------------- RoM on a Gated DeltaNet layer (Sec. 5.2, Table 3)
+namespace {
+struct GdnPlan {              // byte offsets inside the workspace
+  size_t total;
+  size_t expert_idx, gate, counts, offsets, perm, inv_perm, tok_of_pos, block_counts, logits;
+  size_t proj, proj_sorted, qkv, y, op_sorted, conv_tmp;
+};
+
+int check_gdn_dims(const rom_gdn_dims *d) {
+  if (!d) return ROM_E_INVAL;
+  if (d->dtype != ROM_DTYPE_F32 && d->dtype != ROM_DTYPE_BF16) return ROM_E_INVAL;
+  if (d->gate_mode != 0 && d->gate_mode != 1) return ROM_E_INVAL;
+  if (d->d_model <= 0 || d->n_heads <= 0 || d->d_k <= 0 || d->d_v <= 0 || d->n_experts <= 0) return ROM_E_INVAL;
+  if (d->top_k < 1 || d->top_k > d->n_experts) return ROM_E_INVAL;
+  if (d->dtype != ROM_DTYPE_BF16 || d->d_conv != 4 || !gdn_supported(d->d_k, d->d_v)) return ROM_E_UNSUPPORTED;
+  if (d->n_experts > 64 || d->top_k > 8) return ROM_E_UNSUPPORTED;
+  if (d->n_heads % 4 != 0 || d->d_model % 8 != 0 || d->n_heads > 16384) return ROM_E_UNSUPPORTED;
+  return ROM_OK;
+}
+
+GdnPlan make_gdn_plan(const rom_gdn_dims *d, int64_t n_seq, int64_t seq_len) {
+  GdnPlan p;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off += (bytes + kAlign - 1) / kAlign * kAlign;
+    return at;
+  };
+  const size_t N = static_cast<size_t>(n_seq * seq_len), K = d->top_k, S = N * K, E = d->n_experts;
+  const size_t H = d->n_heads, Dk = H * d->d_k, Dv = H * d->d_v, Dm = d->d_model;
+  const size_t Dp = 2 * Dv + 2 * Dk + 2 * H, Dc = 2 * Dk + Dv;
+  p.expert_idx = take(S * 4);
+  p.gate = take(S * 4);
+  p.counts = take(E * 4);
+  p.offsets = take((E + 1) * 4);
+  p.perm = take(S * 4);
+  p.inv_perm = take(S * 4);
+  p.tok_of_pos = take(S * 4);
+  p.block_counts = take(static_cast<size_t>(route_blocks(static_cast<int64_t>(S))) * E * 4);
+  p.logits = take(N * E * 4);
+  p.proj = take(N * Dp * 2);
+  p.proj_sorted = K > 1 ? take(S * Dp * 2) : kNone;
+  p.qkv = take(N * Dc * 2);
+  p.y = take(N * Dv * 2);
+  p.op_sorted = K > 1 ? take(S * Dm * 2) : kNone;
+  p.conv_tmp = take(seq_len > kConvInPlaceMaxLen ? static_cast<size_t>(n_seq) * Dc * 3 * 4 : 0);
+  p.total = off;
+  return p;
+}
+}  // namespace
+
+size_t rom_gdn_workspace_bytes(const rom_gdn_dims *dims, int64_t B, int64_t L) {
+  if (check_gdn_dims(dims) != ROM_OK || B < 0 || L < 0) return 0;
+  return make_gdn_plan(dims, B > 0 ? B : 1, L > 0 ? L : 1).total;
+}
+
+int rom_gdn_workspace_layout(const rom_gdn_dims *dims, int64_t B, int64_t L, rom_gdn_ws_layout *layout) {
+  const int rc = check_gdn_dims(dims);
+  if (rc != ROM_OK) return rc;
+  if (!layout || B < 0 || L < 0) return ROM_E_INVAL;
+  const GdnPlan p = make_gdn_plan(dims, B > 0 ? B : 1, L > 0 ? L : 1);
+  layout->total_bytes = p.total;
+  layout->expert_idx = p.expert_idx;
+  layout->gate = p.gate;
+  layout->counts = p.counts;
+  layout->offsets = p.offsets;
+  layout->perm = p.perm;
+  layout->inv_perm = p.inv_perm;
+  layout->logits = p.logits;
+  layout->proj = p.proj;
+  layout->qkv = p.qkv;
+  layout->y = p.y;
+  return ROM_OK;
+}
+
+int rom_gdn_forward(const rom_gdn_dims *d, const rom_gdn_weights *w, const void *x, int64_t B, int64_t L, float eps,
+                    const float *conv_in, const float *ssm_in, void *out, float *conv_out, float *ssm_out, void *ws,
+                    size_t ws_bytes, void *hip_stream) {
+  int rc = check_gdn_dims(d);
+  if (rc != ROM_OK) return rc;
+  if (!w) return ROM_E_INVAL;
+  {
+    const void *req[] = {w->w_router, w->w_in, w->conv_w, w->dt_bias, w->A_log, w->norm_w, w->w_out};
+    for (const void *ptr : req)
+      if (!ptr || !aligned16(ptr)) return ROM_E_INVAL;
+    if ((w->b_router && !aligned16(w->b_router)) || (w->conv_b && !aligned16(w->conv_b))) return ROM_E_INVAL;
+  }
+  if (B < 0 || L < 0 || !(eps >= 0.0f)) return ROM_E_INVAL;
+  if (B == 0 || L == 0) return ROM_OK;
+  if (!x || !out || !ws || x == out) return ROM_E_INVAL;
+  if (!aligned16(x) || !aligned16(out) || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return ROM_E_INVAL;
+  if (B * L * d->top_k > (1ll << 30) || B > 65535) return ROM_E_UNSUPPORTED;
+  {
+    const float *states[] = {conv_in, ssm_in, conv_out, ssm_out};
+    for (const float *ptr : states)
+      if (ptr && !aligned16(ptr)) return ROM_E_INVAL;
+    if (L > kConvInPlaceMaxLen && ((conv_in && conv_in == conv_out) || (ssm_in && ssm_in == ssm_out))) return ROM_E_INVAL;
+  }
+  const int64_t N = B * L;
+  const GdnPlan p = make_gdn_plan(d, B, L);
+  if (ws_bytes < p.total) return ROM_E_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  char *base = static_cast<char *>(ws);
+  auto at = [&](size_t off) { return base + off; };
+  const int K = d->top_k, E = d->n_experts, H = d->n_heads, Dm = d->d_model;
+  const int Dk = H * d->d_k, Dv = H * d->d_v, Dp = 2 * Dv + 2 * Dk + 2 * H, Dc = 2 * Dk + Dv;
+  const bool multi = K > 1;
+  const int64_t S = N * K;
+  float *gate = reinterpret_cast<float *>(at(p.gate));
+  int32_t *offsets = reinterpret_cast<int32_t *>(at(p.offsets));
+  int32_t *inv_perm = reinterpret_cast<int32_t *>(at(p.inv_perm));
+  int32_t *tok_of_pos = reinterpret_cast<int32_t *>(at(p.tok_of_pos));
+
+  rom_dims rd;
+  memset(&rd, 0, sizeof(rd));
+  rd.d_model = Dm; rd.d_inner = Dv; rd.n_experts = E; rd.top_k = K; rd.n_experts_xdt = E;
+  rd.dtype = d->dtype; rd.gate_mode = d->gate_mode;
+  rom_weights rw;
+  memset(&rw, 0, sizeof(rw));
+  rw.w_router = w->w_router; rw.b_router = w->b_router;
+  StageMark mark;
+  rc = route_into(&rd, &rw, x, N, reinterpret_cast<int32_t *>(at(p.expert_idx)), gate,
+                  reinterpret_cast<int32_t *>(at(p.counts)), offsets, reinterpret_cast<int32_t *>(at(p.perm)), inv_perm,
+                  tok_of_pos, reinterpret_cast<int32_t *>(at(p.block_counts)), reinterpret_cast<float *>(at(p.logits)),
+                  nullptr, nullptr, s, &mark);
+  if (rc != ROM_OK) return rc;
+
+  // input projection z | q | k | v | b | a: one routed GEMM, rows back in token order
+  mark.begin(ROM_STAGE_IN_PROJ, s);
+  GemmArgs ga;
+  memset(&ga, 0, sizeof(ga));
+  ga.dtype = d->dtype;
+  ga.A = x; ga.lda = Dm; ga.a_rows = tok_of_pos; ga.a_span = N * Dm;
+  ga.W = w->w_in; ga.N = Dp; ga.K = Dm;
+  ga.n_groups = E; ga.M = S; ga.offsets = offsets;
+  ga.C = multi ? at(p.proj_sorted) : at(p.proj); ga.ldc = Dp; ga.c_rows = multi ? nullptr : tok_of_pos;
+  ROM_TRY(launch_grouped_gemm(ga, s));
+  if (multi)
+    ROM_TRY(launch_slot_sum(0, 0, at(p.proj_sorted), Dp, at(p.proj), Dp, inv_perm, N, K, Dp, nullptr, 0, nullptr, s));
+  mark.end(ROM_STAGE_IN_PROJ, s);
+
+  // short conv + SiLU over the channels q | k | v
+  mark.begin(ROM_STAGE_CONV, s);
+  {
+    float *ctmp = reinterpret_cast<float *>(at(p.conv_tmp));
+    const bool beside = conv_out && L > kConvInPlaceMaxLen;
+    ROM_TRY(launch_conv_silu(d->dtype, at(p.proj) + static_cast<size_t>(Dv) * 2, Dp, w->conv_w, w->conv_b, conv_in,
+                             beside ? ctmp : conv_out, at(p.qkv), B, L, Dc, s));
+    if (beside) {
+      const int64_t n = B * Dc * 3;
+      hipLaunchKernelGGL(copy_f32_kernel, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, s, ctmp, conv_out, n);
+      ROM_TRY(hipGetLastError());
+    }
+  }
+  mark.end(ROM_STAGE_CONV, s);
+
+  // delta rule, head norm, SiLU(z) gate
+  mark.begin(ROM_STAGE_SCAN, s);
+  ROM_TRY(launch_gdn_scan(at(p.qkv), Dc, 0, Dk, 2 * Dk, at(p.proj), Dp, Dv + Dc, Dv + Dc + H, w->dt_bias, w->A_log, w->norm_w,
+                          eps, B, L, H, d->d_k, ssm_in, ssm_out, at(p.y), Dv, s));
+  mark.end(ROM_STAGE_SCAN, s);
+
+  // output projection and the gate-weighted combine
+  mark.begin(ROM_STAGE_OUT_PROJ, s);
+  memset(&ga, 0, sizeof(ga));
+  ga.dtype = d->dtype;
+  ga.A = at(p.y); ga.lda = Dv; ga.a_rows = tok_of_pos; ga.a_span = N * Dv;
+  ga.W = w->w_out; ga.N = Dm; ga.K = Dv;
+  ga.n_groups = E; ga.M = S; ga.offsets = offsets;
+  if (multi) {
+    ga.C = at(p.op_sorted); ga.ldc = Dm;
+    ROM_TRY(launch_grouped_gemm(ga, s));
+    mark.end(ROM_STAGE_OUT_PROJ, s);
+    mark.begin(ROM_STAGE_COMBINE, s);
+    ROM_TRY(launch_combine(d->dtype, at(p.op_sorted), inv_perm, gate, out, N, K, Dm, nullptr, s));
+    mark.end(ROM_STAGE_COMBINE, s);
+  } else {
+    ga.C = out; ga.ldc = Dm; ga.c_rows = tok_of_pos; ga.row_scale = gate;
+    ROM_TRY(launch_grouped_gemm(ga, s));
+    mark.end(ROM_STAGE_OUT_PROJ, s);
+  }
+  return ROM_OK;
+}
+
 size_t rom_backward_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L) {
   if (check_dims(dims) != ROM_OK || B < 0 || L < 0) return 0;
   return make_bwd_plan(dims, B > 0 ? B : 1, L > 0 ? L : 1).total;

@@ -1,0 +1,484 @@
+// RoM on a Gated DeltaNet layer (Sec. 5.2, Table 3): the sequence part between the routed input and
+// output projections - per head the gated delta rule on the state S (d_v x d_k)
+//     S_t = exp(g_t) S_{t-1} (I - beta_t k_t k_t^T) + beta_t v_t k_t^T,     o_t = S_t q_t
+// with q, k L2-normalised per head, then the per-head RMS norm and the SiLU(z) gate.  gfx950 only,
+// bf16 activations, d_v = 64, d_k = 64 or 128.
+//
+// Chunked form (chunks of 64 steps, cum_t = sum_{r <= t} g_r inside the chunk, gamma = exp(cum)): the
+// rank-one updates u_t = beta_t (v_t - exp(g_t) S_{t-1} k_t) of a chunk obey the unit lower-triangular
+// system
+//     (I + A) U = diag(beta) (V - diag(gamma) K S_0^T),   A[t][s] = beta_t exp(cum_t - cum_s) (k_t . k_s), s < t,
+// and then  O = diag(gamma) Q S_0^T + (Q K^T o exp(cum_t - cum_s), s <= t) U,
+//           S_new = gamma_64 S_0 + sum_s exp(cum_64 - cum_s) u_s k_s^T.
+// Everything but the inverse is a small matrix product on v_mfma_f32_16x16x32_bf16; T = (I + A)^-1 is
+// computed in fp32 by one wavefront: the four 16 x 16 diagonal blocks by forward substitution (a lane
+// per column), the six blocks below them by block substitution on v_mfma_f32_16x16x4_f32.
+// A workgroup (4 wavefronts) owns one (sequence, head) and walks its chunks in order; wavefront w
+// holds the state columns S^T[:, 16w .. 16w+15] (d_k x 16 values of d_v) in accumulators, as the
+// Mamba2 kernel does, and the products that contract over steps or over d_k take their second
+// operand straight from accumulators (the contraction index permuted alike on the other side).
+#include "rom_internal.h"
+
+#include <atomic>
+#include <mutex>
+
+namespace rom {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+
+constexpr int kQ = 64;          // steps per chunk
+constexpr int kV = 64;          // value channels per head
+constexpr float kLog2e = 1.44269504088896341f;
+constexpr float kL2Eps = 1e-6f;
+
+__device__ __forceinline__ float softplus_f32(float v) { return v > 20.0f ? v : log1pf(__expf(v)); }
+
+template <int NS>
+struct GdnSmem {
+  union {
+    struct {
+      bf16_t kn[kQ][NS + 8];    // normalised keys, step-major
+      bf16_t qr[kQ][NS + 8];    // raw queries, step-major
+    } in;
+    float tm[kQ][kQ + 4];       // after the scores: T = (I + A)^-1 in fp32
+  } u;
+  union {
+    float am[kQ][kQ + 4];       // A (strictly lower triangle), fp32
+    float y[kQ][kV + 4];        // later in the chunk: the output tile
+  } a;
+  bf16_t vt[kQ][kV + 8];        // values, step-major
+  bf16_t kw_t[NS][kQ + 8];      // exp(cum_64 - cum_s) k_s, channel-major, 16-byte pieces swizzled
+  bf16_t tb[kQ][kQ + 8];        // T in bf16 [t][s]
+  bf16_t gs[kQ][kQ + 8];        // exp(cum_t - cum_s) (q_t . k_s), s <= t, [t][s]
+  float cum[kQ], ecum[kQ], beta[kQ], rq[kQ];
+};
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_or_zero(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
+}
+// inclusive prefix sum over the 64 lanes (row shifts, then lane 15 / 31 broadcasts)
+__device__ __forceinline__ float wave_inclusive_sum(float v) {
+  v += dpp_or_zero<0x111, 0xF>(v);
+  v += dpp_or_zero<0x112, 0xF>(v);
+  v += dpp_or_zero<0x114, 0xF>(v);
+  v += dpp_or_zero<0x118, 0xF>(v);
+  v += dpp_or_zero<0x142, 0xA>(v);
+  v += dpp_or_zero<0x143, 0xC>(v);
+  return v;
+}
+
+__device__ __forceinline__ float bf16_elem(const u32x4_t &v, int m) {
+  const unsigned int w = v[m >> 1];
+  return __uint_as_float((m & 1) ? (w & 0xFFFF0000u) : (w << 16));
+}
+__device__ __forceinline__ float sum_sq8(const u32x4_t &v) {
+  float s = 0.0f;
+#pragma unroll
+  for (int m = 0; m < 8; ++m) {
+    const float f = bf16_elem(v, m);
+    s = fmaf(f, f, s);
+  }
+  return s;
+}
+// sum over the WIDTH (8 or 16) consecutive lanes that share a row
+template <int WIDTH>
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int off = 1; off < WIDTH; off <<= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+// eight 16-byte pieces (8 columns of 8 steps), step i scaled by f[i] -> column-major 16-byte segments
+template <int PITCH>
+__device__ __forceinline__ void park_scaled_8x8(const u32x4_t (&v)[8], const float (&f)[8], bf16_t (*dst)[PITCH], int col0,
+                                                int step0) {
+#pragma unroll
+  for (int m = 0; m < 8; ++m) {
+    u32x4_t seg;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+      seg[a] = pack_bf16x2(f[2 * a] * bf16_elem(v[2 * a], m), f[2 * a + 1] * bf16_elem(v[2 * a + 1], m));
+    *reinterpret_cast<u32x4_t *>(&dst[col0 + m][step0]) = seg;
+  }
+}
+
+__device__ __forceinline__ bf16x8_t as_frag(const u32x4_t &v) { return __builtin_bit_cast(bf16x8_t, v); }
+__device__ __forceinline__ bf16x8_t frag_from_halves(const u32x2_t &lo, const u32x2_t &hi) {
+  const u32x4_t v = {lo[0], lo[1], hi[0], hi[1]};
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+// two accumulator quads (rows 4g.. of two consecutive 16-row blocks) as the B operand of a 32-wide step
+__device__ __forceinline__ bf16x8_t frag_from_acc(const f32x4_t &lo, const f32x4_t &hi) {
+  const u32x4_t v = {pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3])};
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+// the matching A operand: row `row` of a step-major bf16 array, columns base + 4g .. and base + 16 + 4g ..
+template <int PITCH>
+__device__ __forceinline__ bf16x8_t frag_perm(const bf16_t (*src)[PITCH], int row, int base, int g) {
+  const u32x2_t lo = *reinterpret_cast<const u32x2_t *>(&src[row][base + 4 * g]);
+  const u32x2_t hi = *reinterpret_cast<const u32x2_t *>(&src[row][base + 16 + 4 * g]);
+  return frag_from_halves(lo, hi);
+}
+
+// T = (I + A)^-1 for the 64 x 64 unit lower-triangular I + A, by ONE wavefront: am -> tm (fp32), tb (bf16).
+__device__ __forceinline__ void invert_unit_lower(const float (*am)[kQ + 4], float (*tm)[kQ + 4], bf16_t (*tb)[kQ + 8],
+                                                  int lane) {
+  const int g = lane >> 4, c = lane & 15;
+  // diagonal blocks: lane (g, c) solves column c of block g by forward substitution
+  {
+    float x[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float acc = r == c ? 1.0f : 0.0f;
+#pragma unroll
+      for (int m = 0; m < r; ++m) acc = fmaf(-am[16 * g + r][16 * g + m], x[m], acc);
+      x[r] = acc;
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      tm[16 * g + r][16 * g + c] = x[r];
+      tb[16 * g + r][16 * g + c] = f32_to_bf16(x[r]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)            // blocks above the diagonal are zero
+        if (j > g) tb[16 * g + r][16 * j + c] = 0;
+    }
+  }
+  // blocks below the diagonal, by distance from it: T_ij = -T_ii sum_{m = j .. i-1} A_im T_mj
+#pragma unroll
+  for (int d = 1; d < 4; ++d)
+#pragma unroll
+    for (int j = 0; j + d < 4; ++j) {
+      const int i = j + d;
+      f32x4_t macc = {0.0f, 0.0f, 0.0f, 0.0f};
+      for (int m = j; m < i; ++m)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          macc = __builtin_amdgcn_mfma_f32_16x16x4f32(am[16 * i + c][16 * m + 4 * q + g], tm[16 * m + 4 * q + g][16 * j + c], macc,
+                                                       0, 0, 0);
+      // second product with the accumulators as the B operand: contraction slot (q, g) <-> k = 4 g + q
+      f32x4_t res = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        res = __builtin_amdgcn_mfma_f32_16x16x4f32(tm[16 * i + c][16 * i + 4 * g + q], macc[q], res, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        tm[16 * i + 4 * g + r][16 * j + c] = -res[r];
+        tb[16 * i + 4 * g + r][16 * j + c] = f32_to_bf16(-res[r]);
+      }
+    }
+}
+
+// Grid (n_heads, B).
+//   qkv   bf16 [B*L, ld_qkv] after conv + SiLU: q of head h at q_col + NS h, k at k_col + NS h, v at v_col + 64 h
+//   proj  bf16 [B*L, ld_p]: z of head h at columns 64 h, the beta logit at b_col + h, the decay logit at a_col + h
+//   s_in / s_out f32 [B][H][NS][64] (S^T: [d_k][d_v]) or NULL;   y bf16 [B*L, ld_y]: RMSNorm_head(o) * norm_w * SiLU(z)
+template <int NS>
+__global__ __launch_bounds__(256, 1) void gdn_kernel(const bf16_t *__restrict__ qkv, int64_t ld_qkv, int q_col, int k_col,
+                                                     int v_col, const bf16_t *__restrict__ proj, int64_t ld_p, int b_col,
+                                                     int a_col, const float *__restrict__ dt_bias,
+                                                     const float *__restrict__ A_log, const float *__restrict__ norm_w,
+                                                     float eps, int64_t L, const float *s_in, float *s_out,
+                                                     bf16_t *__restrict__ y, int64_t ld_y) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  GdnSmem<NS> &sm = *reinterpret_cast<GdnSmem<NS> *>(smem_raw);
+  constexpr int kNB = NS / 16, kKS = NS / 32;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, c = lane & 15;
+  const int h = blockIdx.x, n_heads = gridDim.x;
+  const int64_t b = blockIdx.y;
+  const float rate = __expf(A_log[h]), bias = dt_bias[h];
+  const bf16_t *qkv_b = qkv + b * L * ld_qkv;
+  const bf16_t *proj_b = proj + b * L * ld_p;
+  const float q_scale = rsqrtf(static_cast<float>(NS));
+
+  // state: sacc[nb][r] = S^T[d_k index 16 nb + 4 g + r][d_v index 16 wave + c]
+  f32x4_t sacc[kNB];
+  const int64_t s_stride = static_cast<int64_t>(NS) * kV;
+#pragma unroll
+  for (int nb = 0; nb < kNB; ++nb) sacc[nb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+  if (s_in) {
+    const float *sp = s_in + (b * n_heads + h) * s_stride + wave * 16 + c;
+#pragma unroll
+    for (int nb = 0; nb < kNB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) sacc[nb][r] = sp[(16 * nb + 4 * g + r) * kV];
+  }
+
+  // roles while a chunk is parked: threads [0, NS) keys (8 x 8 blocks), the next 64 values; all: queries
+  const bool is_k = tid < NS;
+  const bool is_v = tid >= NS && tid < NS + 64;
+  const int lt = is_k ? tid : tid - NS;
+  const int n_co = is_k ? NS / 8 : kV / 8;
+  const int so = lt / n_co, co = lt % n_co;
+  const int so_phys = so ^ (co & 7);
+  const int t_col = is_k ? k_col + h * NS + 8 * co : v_col + h * kV + 8 * co;
+  const int e_row = tid >> 3, e_po = tid & 7;
+
+  for (int64_t t0 = 0; t0 < L; t0 += kQ) {
+    const int64_t te = L;
+    // per step: beta, log decay, cumulative log decay (every wavefront for itself, one step per lane)
+    float beta = 0.0f, gl = 0.0f;
+    if (t0 + lane < te) {
+      const bf16_t *row = proj_b + (t0 + lane) * ld_p;
+      beta = fast_rcp(1.0f + __expf(-bf16_to_f32(row[b_col + h])));
+      gl = -rate * softplus_f32(bf16_to_f32(row[a_col + h]) + bias);
+    }
+    const float cum = wave_inclusive_sum(gl);
+    const float cum_last = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cum), 63));
+
+    __syncthreads();                // the chunk before this one is done with the LDS
+    if (is_k || is_v) {
+      u32x4_t pv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int64_t t = t0 + 8 * so + i;
+        pv[i] = *reinterpret_cast<const u32x4_t *>(qkv_b + (t < te ? t : te - 1) * ld_qkv + t_col);
+        if (t >= te) pv[i] = u32x4_t{0u, 0u, 0u, 0u};
+      }
+      if (is_k) {
+        // row norms: the n_co lanes with this `so` hold the eight steps' other column blocks
+        const float w_lane = fast_exp2((cum_last - cum) * kLog2e);
+        float rk[8], f[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          rk[i] = rsqrtf(group_sum<NS / 8>(sum_sq8(pv[i])) + kL2Eps);
+          f[i] = rk[i] * __shfl(w_lane, 8 * so + i);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          u32x4_t kv;
+#pragma unroll
+          for (int a = 0; a < 4; ++a) kv[a] = pack_bf16x2(rk[i] * bf16_elem(pv[i], 2 * a), rk[i] * bf16_elem(pv[i], 2 * a + 1));
+          *reinterpret_cast<u32x4_t *>(&sm.u.in.kn[8 * so + i][8 * co]) = kv;
+        }
+        park_scaled_8x8<kQ + 8>(pv, f, sm.kw_t, 8 * co, 8 * so_phys);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t *>(&sm.vt[8 * so + i][8 * co]) = pv[i];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NS / 32; ++i) {             // queries: 64 rows of NS / 8 pieces, raw; their norms
+      const int piece = tid + 256 * i;
+      const int row = piece / (NS / 8), oc = piece % (NS / 8);
+      const int64_t t = t0 + row;
+      u32x4_t v = *reinterpret_cast<const u32x4_t *>(qkv_b + (t < te ? t : te - 1) * ld_qkv + q_col + h * NS + 8 * oc);
+      if (t >= te) v = u32x4_t{0u, 0u, 0u, 0u};
+      *reinterpret_cast<u32x4_t *>(&sm.u.in.qr[row][8 * oc]) = v;
+      const float ss = group_sum<NS / 8>(sum_sq8(v));
+      if (oc == 0) sm.rq[row] = rsqrtf(ss + kL2Eps) * q_scale;
+    }
+    if (wave == 3) {
+      sm.cum[lane] = cum;
+      sm.ecum[lane] = fast_exp2(cum * kLog2e);
+      sm.beta[lane] = beta;
+    }
+    __syncthreads();
+
+    // ---- scores of this wavefront's 16 steps t = 16 wave + c against all s (computed transposed),
+    //      and the two products with the state the chunk starts from
+    {
+      const float cum_t = sm.cum[16 * wave + c], beta_t = sm.beta[16 * wave + c];
+#pragma unroll
+      for (int sb = 0; sb < 4; ++sb) {
+        f32x4_t kk = {0.0f, 0.0f, 0.0f, 0.0f}, qk = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (sb <= wave) {
+#pragma unroll
+          for (int ks = 0; ks < kKS; ++ks) {
+            const bf16x8_t fa = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.u.in.kn[16 * sb + c][32 * ks + 8 * g]));
+            const bf16x8_t fk = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.u.in.kn[16 * wave + c][32 * ks + 8 * g]));
+            const bf16x8_t fq = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.u.in.qr[16 * wave + c][32 * ks + 8 * g]));
+            kk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fk, kk, 0, 0, 0);
+            qk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fq, qk, 0, 0, 0);
+          }
+        }
+        const f32x4_t cum_s = *reinterpret_cast<const f32x4_t *>(&sm.cum[16 * sb + 4 * g]);
+        f32x4_t av;
+        float gv[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int s = 16 * sb + 4 * g + r, t = 16 * wave + c;
+          const float dec = s <= t ? fast_exp2((cum_t - cum_s[r]) * kLog2e) : 0.0f;
+          av[r] = s < t ? beta_t * dec * kk[r] : 0.0f;
+          gv[r] = dec * qk[r];
+        }
+        *reinterpret_cast<f32x4_t *>(&sm.a.am[16 * wave + c][16 * sb + 4 * g]) = av;
+        const u32x2_t packed = {pack_bf16x2(gv[0], gv[1]), pack_bf16x2(gv[2], gv[3])};
+        *reinterpret_cast<u32x2_t *>(&sm.gs[16 * wave + c][16 * sb + 4 * g]) = packed;
+      }
+    }
+    bf16x8_t sop[kKS];
+#pragma unroll
+    for (int ks = 0; ks < kKS; ++ks) sop[ks] = frag_from_acc(sacc[2 * ks], sacc[2 * ks + 1]);
+    f32x4_t rhs[4], oacc[4];
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb) {
+      f32x4_t pacc = {0.0f, 0.0f, 0.0f, 0.0f};
+      oacc[tb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int ks = 0; ks < kKS; ++ks) {
+        pacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag_perm<NS + 8>(sm.u.in.kn, 16 * tb + c, 32 * ks, g), sop[ks], pacc, 0, 0, 0);
+        oacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag_perm<NS + 8>(sm.u.in.qr, 16 * tb + c, 32 * ks, g), sop[ks],
+                                                           oacc[tb], 0, 0, 0);
+      }
+      const f32x4_t e = *reinterpret_cast<const f32x4_t *>(&sm.ecum[16 * tb + 4 * g]);
+      const f32x4_t bt = *reinterpret_cast<const f32x4_t *>(&sm.beta[16 * tb + 4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float vv = bf16_to_f32(sm.vt[16 * tb + 4 * g + r][16 * wave + c]);
+        rhs[tb][r] = bt[r] * (vv - e[r] * pacc[r]);         // beta_t (v_t - gamma_t S_0 k_t)
+        oacc[tb][r] *= e[r];                                  // gamma_t S_0 q_t
+      }
+    }
+    __syncthreads();                // A is complete; the step-major keys and queries are no longer read
+
+    if (wave == 0) invert_unit_lower(sm.a.am, sm.u.tm, sm.tb, lane);
+    __syncthreads();
+
+    // ---- U = T rhs (rows t, this wavefront's 16 value channels); the contraction runs over steps,
+    //      with rhs taken from the accumulators
+    f32x4_t uacc[4];
+    {
+      bf16x8_t rop[2];
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2) rop[k2] = frag_from_acc(rhs[2 * k2], rhs[2 * k2 + 1]);
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb) {
+        uacc[tb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2)
+          if (k2 == 0 || tb >= 2)
+            uacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag_perm<kQ + 8>(sm.tb, 16 * tb + c, 32 * k2, g), rop[k2], uacc[tb],
+                                                               0, 0, 0);
+      }
+    }
+    bf16x8_t uop[2];
+#pragma unroll
+    for (int k2 = 0; k2 < 2; ++k2) uop[k2] = frag_from_acc(uacc[2 * k2], uacc[2 * k2 + 1]);
+    // inside the chunk: O[t] += sum_{s <= t} exp(cum_t - cum_s) (q_t . k_s) u_s
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2)
+        if (k2 == 0 || tb >= 2)
+          oacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag_perm<kQ + 8>(sm.gs, 16 * tb + c, 32 * k2, g), uop[k2], oacc[tb], 0,
+                                                             0, 0);
+    // state at the chunk's end: S^T = gamma_64 S^T + sum_s (exp(cum_64 - cum_s) k_s) u_s^T
+    {
+      const float dec = fast_exp2(cum_last * kLog2e);
+#pragma unroll
+      for (int nb = 0; nb < kNB; ++nb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sacc[nb][r] *= dec;
+        const int row = 16 * nb + c, sw = (row >> 3) & 7;
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+          // steps 32 k2 + 4 g .. +3 and 32 k2 + 16 + 4 g .. +3 of the swizzled channel-major array
+          const int p_lo = (4 * k2 + (g >> 1)) ^ sw, p_hi = (4 * k2 + 2 + (g >> 1)) ^ sw;
+          const u32x2_t lo = *reinterpret_cast<const u32x2_t *>(&sm.kw_t[row][8 * p_lo + 4 * (g & 1)]);
+          const u32x2_t hi = *reinterpret_cast<const u32x2_t *>(&sm.kw_t[row][8 * p_hi + 4 * (g & 1)]);
+          sacc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag_from_halves(lo, hi), uop[k2], sacc[nb], 0, 0, 0);
+        }
+      }
+    }
+    // ---- output rows: query norm and scale, RMS norm over the head's 64 channels, SiLU(z) gate
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb) {
+      const f32x4_t rq = *reinterpret_cast<const f32x4_t *>(&sm.rq[16 * tb + 4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) sm.a.y[16 * tb + 4 * g + r][16 * wave + c] = oacc[tb][r] * rq[r];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int row = e_row + 32 * i;
+      const int64_t t = t0 + row;
+      const f32x4_t y0 = *reinterpret_cast<const f32x4_t *>(&sm.a.y[row][8 * e_po]);
+      const f32x4_t y1 = *reinterpret_cast<const f32x4_t *>(&sm.a.y[row][8 * e_po + 4]);
+      float ss = 0.0f;
+#pragma unroll
+      for (int m = 0; m < 4; ++m) ss = fmaf(y0[m], y0[m], fmaf(y1[m], y1[m], ss));
+      const float rstd = rsqrtf(group_sum<8>(ss) * (1.0f / kV) + eps);
+      const int64_t tc = t < te ? t : te - 1;
+      const u32x4_t zv = *reinterpret_cast<const u32x4_t *>(proj_b + tc * ld_p + h * kV + 8 * e_po);
+      const f32x4_t w0 = *reinterpret_cast<const f32x4_t *>(norm_w + 8 * e_po);
+      const f32x4_t w1 = *reinterpret_cast<const f32x4_t *>(norm_w + 8 * e_po + 4);
+      float o[8];
+#pragma unroll
+      for (int m = 0; m < 8; ++m)
+        o[m] = (m < 4 ? y0[m & 3] * w0[m & 3] : y1[m & 3] * w1[m & 3]) * rstd * silu_f32(bf16_elem(zv, m));
+      const u32x4_t ov = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])};
+      if (t < te) *reinterpret_cast<u32x4_t *>(y + (b * L + t) * ld_y + h * kV + 8 * e_po) = ov;
+    }
+  }
+
+  if (s_out) {
+    float *sp = s_out + (b * n_heads + h) * s_stride + wave * 16 + c;
+#pragma unroll
+    for (int nb = 0; nb < kNB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) sp[(16 * nb + 4 * g + r) * kV] = sacc[nb][r];
+  }
+}
+
+template <int NS>
+hipError_t gdn_allow_lds() {
+  // more than 64 KiB of dynamic LDS: a function attribute, set once per device
+  static std::mutex mu;
+  static std::atomic<bool> done[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!done[dev].load(std::memory_order_acquire)) {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!done[dev].load(std::memory_order_relaxed)) {
+      e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gdn_kernel<NS>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              static_cast<int>(sizeof(GdnSmem<NS>)));
+      if (e != hipSuccess) return e;
+      done[dev].store(true, std::memory_order_release);
+    }
+  }
+  return hipSuccess;
+}
+
+template <int NS>
+hipError_t gdn_dispatch(const bf16_t *qkv, int64_t ld_qkv, int q_col, int k_col, int v_col, const bf16_t *proj, int64_t ld_p,
+                        int b_col, int a_col, const float *dt_bias, const float *A_log, const float *norm_w, float eps,
+                        int64_t B, int64_t L, int n_heads, const float *s_in, float *s_out, bf16_t *y, int64_t ld_y,
+                        hipStream_t s) {
+  hipError_t e = gdn_allow_lds<NS>();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((gdn_kernel<NS>), dim3(static_cast<unsigned>(n_heads), static_cast<unsigned>(B)), dim3(256),
+                     sizeof(GdnSmem<NS>), s, qkv, ld_qkv, q_col, k_col, v_col, proj, ld_p, b_col, a_col, dt_bias, A_log, norm_w,
+                     eps, L, s_in, s_out, y, ld_y);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool gdn_supported(int d_k, int d_v) { return d_v == kV && (d_k == 64 || d_k == 128); }
+
+hipError_t launch_gdn_scan(const void *qkv, int64_t ld_qkv, int q_col, int k_col, int v_col, const void *proj, int64_t ld_p,
+                           int b_col, int a_col, const float *dt_bias, const float *A_log, const float *norm_w, float eps,
+                           int64_t B, int64_t L, int n_heads, int d_k, const float *s_in, float *s_out, void *y,
+                           int64_t ld_y, hipStream_t s) {
+  if (B * L <= 0) return hipSuccess;
+  if (B > 65535) return hipErrorInvalidValue;
+  const bf16_t *qp = static_cast<const bf16_t *>(qkv), *pp = static_cast<const bf16_t *>(proj);
+  if (d_k == 128)
+    return gdn_dispatch<128>(qp, ld_qkv, q_col, k_col, v_col, pp, ld_p, b_col, a_col, dt_bias, A_log, norm_w, eps, B, L,
+                             n_heads, s_in, s_out, static_cast<bf16_t *>(y), ld_y, s);
+  if (d_k == 64)
+    return gdn_dispatch<64>(qp, ld_qkv, q_col, k_col, v_col, pp, ld_p, b_col, a_col, dt_bias, A_log, norm_w, eps, B, L, n_heads,
+                            s_in, s_out, static_cast<bf16_t *>(y), ld_y, s);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace rom

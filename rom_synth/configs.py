@@ -325,7 +325,7 @@ GDN_CONFIGS: Dict[str, GdnConfig] = {
     "gdn_small": GdnConfig("gdn_small", 50, 2, 200, 256, 8, 64, 64, 4, 1, 0),
     "gdn_mid": GdnConfig("gdn_mid", 51, 2, 1500, 512, 16, 64, 64, 6, 2, 1),
     # the headline layer's counterpart: 16K context, d_model 2048, 8 experts top-1
-    "gdn_cfg2": GdnConfig("gdn_cfg2", 52, 1, 16384, 2048, 32, 64, 128, 8, 1, 0,
+    "gdn_cfg2": GdnConfig("gdn_cfg2", 52, 1, 16384, 2048, 32, 64, 64, 8, 1, 0,
                           weight_std=0.02 / float(np.sqrt(2 * 48)), rms_norm_x=True),
 }
 

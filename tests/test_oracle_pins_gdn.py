@@ -219,7 +219,7 @@ def test_state_carry_equals_unsplit_and_causality():
 
 def test_gdn_synth_shapes():
     cfg = S.get_gdn_config("gdn_cfg2")
-    assert (cfg.d_kt, cfg.d_vt, cfg.d_in_proj, cfg.d_conv_ch) == (2048, 4096, 12352, 8192)
+    assert (cfg.d_kt, cfg.d_vt, cfg.d_in_proj, cfg.d_conv_ch) == (2048, 2048, 8256, 6144)
     small = S.get_gdn_config("gdn_small")
     w = S.make_gdn_weights(small)
     assert w["w_in"].shape == (4, small.d_in_proj, 256) and w["norm_w"].shape == (small.d_v,)
