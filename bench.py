@@ -10,7 +10,7 @@ events around the dominant kernel (the in projection) only; the per-stage breakd
 second pass with an event at every stage boundary.  Beside the headline: HBM traffic of the
 dominant kernel from two rocprofv3 counter runs of this script, forward timings of the two other
 layer configurations, the load-balance statistics, the shared x/dt variant, forward + backward of
-the layer, RoM on a Mamba2 layer of the same size, a 48-block stack, the FFN-MoE layer, the
+the layer, RoM on a Mamba2 and on a Gated DeltaNet layer of the same width, a 48-block stack, the FFN-MoE layer, the
 recurrent step and the CPU oracle's rate
 (--help lists the switches that skip them; --probe prints issue-rate measurements instead).
 """
@@ -480,6 +480,49 @@ def mamba2_rate(steps, warmup):
     return out
 
 
+def gdn_rate(steps, warmup):
+    """RoM on a Gated DeltaNet layer (Sec. 5.2, Table 3): rom_gdn_forward on d_model 2048, 32 heads of
+    64 key and 64 value channels, 8 experts top-1 - the 16K-token sequence, and the same number of
+    tokens as 8 sequences of 2048 (the recurrence is parallel over sequences x heads only)."""
+    import torch
+    from dataclasses import replace as dc_replace
+    from paper_2506_18145_amd import (RomGdnLayer, rom_profile_collect_calls, rom_profile_enable, rom_profile_select,
+                                      STAGE_NAMES)
+    from rom_synth import get_gdn_config, make_gdn_input, make_gdn_weights
+    out = {}
+    for label, cfg in (("one_sequence", get_gdn_config("gdn_cfg2")),
+                       ("eight_sequences", dc_replace(get_gdn_config("gdn_cfg2"), batch=8, seq_len=2048))):
+        layer = RomGdnLayer(cfg, make_gdn_weights(cfg), device="cuda:0")
+        x = layer.to_device(make_gdn_input(cfg))
+        for _ in range(warmup):
+            layer.forward(x)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        torch.cuda.synchronize()
+        evs[0].record()
+        for i in range(steps):
+            layer.forward(x)
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        ms = _median([evs[i].elapsed_time(evs[i + 1]) for i in range(steps)])
+        rom_profile_select(0xFFFFFFFF)
+        rom_profile_enable(steps)
+        for _ in range(steps):
+            layer.forward(x)
+        torch.cuda.synchronize()
+        per_call = rom_profile_collect_calls(steps)
+        rom_profile_enable(0)
+        stages = {}
+        for nm in STAGE_NAMES:
+            vals = [c[nm] for c in per_call if c[nm] > 0]
+            if vals:
+                stages["delta_rule_norm_gate" if nm == "scan_gate" else nm] = _median(vals)
+        out[label] = {"workload": f"{cfg.name}: B={cfg.batch}, L={cfg.seq_len}, d_model={cfg.d_model}, heads={cfg.n_heads}, "
+                                  f"d_k={cfg.d_k}, d_v={cfg.d_v}, E={cfg.n_experts}, top_k={cfg.top_k}, bf16",
+                      "ms_per_call": ms, "tokens_per_s": cfg.n_tokens / (ms * 1e-3), "stages_ms": stages}
+        del layer, x
+    return out
+
+
 def config_leg(name, steps, warmup):
     """The same measurement on another of the paper-shaped workloads (beside the headline one)."""
     from rom_synth import get_config
@@ -622,6 +665,7 @@ def main():
     ap.add_argument("--no-ffn", action="store_true", help="skip the extra FFN-MoE layer measurement")
     ap.add_argument("--no-backward", action="store_true", help="skip the extra backward-pass measurement")
     ap.add_argument("--no-mamba2", action="store_true", help="skip the RoM-on-Mamba2 layer measurement")
+    ap.add_argument("--no-gdn", action="store_true", help="skip the RoM-on-Gated-DeltaNet layer measurement")
     ap.add_argument("--no-configs", action="store_true", help="skip the legs on the other paper-shaped workloads")
     ap.add_argument("--no-traffic", action="store_true",
                     help="skip the two rocprofv3 counter runs that measure the dominant kernel's HBM traffic")
@@ -724,6 +768,8 @@ def main():
         extra("backward", lambda: backward_rate(cfg, 5, 2))
     if not args.no_mamba2:
         extra("mamba2_variant", lambda: mamba2_rate(10, 3))
+    if not args.no_gdn:
+        extra("gdn_variant", lambda: gdn_rate(5, 2))
     if not args.no_ffn:
         extra("ffn_moe", lambda: ffn_moe_rate(cfg, 2 * cfg.d_model, 20, 20))
     if args.hybrid_layers > 0:

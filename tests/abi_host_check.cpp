@@ -182,6 +182,40 @@ int main() {
     CHECK(rom_mamba2_forward(nullptr, &mw, addr, 1, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
   }
 
+  // ---- RoM on Gated DeltaNet: planning and validation
+  {
+    rom_gdn_dims m;
+    m.d_model = 2048; m.n_heads = 32; m.d_k = 64; m.d_v = 64; m.d_conv = 4;
+    m.n_experts = 8; m.top_k = 2; m.dtype = ROM_DTYPE_BF16; m.gate_mode = 1;
+    for (int64_t B : {int64_t(1), int64_t(8), int64_t(4096)})
+      for (int64_t L : {int64_t(1), int64_t(65), int64_t(2048), int64_t(1) << 17}) {
+        if (B * L > (int64_t(1) << 23)) continue;
+        const size_t bytes = rom_gdn_workspace_bytes(&m, B, L);
+        CHECK(bytes > 0);
+        rom_gdn_ws_layout lay;
+        CHECK(rom_gdn_workspace_layout(&m, B, L, &lay) == ROM_OK);
+        CHECK(lay.total_bytes == bytes && lay.proj < bytes && lay.qkv < bytes && lay.y < bytes);
+        CHECK(lay.proj % 256 == 0 && lay.y % 256 == 0);
+      }
+    rom_gdn_dims bad = m;
+    bad.d_k = 32;        CHECK(rom_gdn_workspace_bytes(&bad, 1, 64) == 0);  bad = m;
+    bad.d_v = 128;       CHECK(rom_gdn_workspace_bytes(&bad, 1, 64) == 0);  bad = m;
+    bad.n_heads = 6;     CHECK(rom_gdn_workspace_bytes(&bad, 1, 64) == 0);  bad = m;
+    bad.dtype = ROM_DTYPE_F32;  CHECK(rom_gdn_workspace_bytes(&bad, 1, 64) == 0);
+    CHECK(rom_gdn_workspace_bytes(nullptr, 1, 64) == 0);
+    CHECK(rom_gdn_workspace_layout(&m, 1, 64, nullptr) == ROM_E_INVAL);
+    rom_gdn_weights gw;
+    std::memset(&gw, 0, sizeof(gw));
+    CHECK(rom_gdn_forward(&m, &gw, addr, 1, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+    gw.w_router = addr; gw.w_in = addr; gw.conv_w = reinterpret_cast<const float *>(addr);
+    gw.dt_bias = gw.A_log = gw.norm_w = reinterpret_cast<const float *>(addr); gw.w_out = addr;
+    CHECK(rom_gdn_forward(&m, &gw, addr, 1, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+    CHECK(rom_gdn_forward(&m, &gw, addr, 0, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_OK);
+    float *st = reinterpret_cast<float *>(addr);
+    CHECK(rom_gdn_forward(&m, &gw, addr, 1, 64, 1e-5f, nullptr, st, addr + 4096, nullptr, st, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_gdn_forward(&m, &gw, addr, 1, 64, 1e-5f, nullptr, nullptr, addr, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+  }
+
   // ---- strings and the profiling bookkeeping
   CHECK(std::strcmp(rom_strerror(ROM_OK), "ok") == 0);
   for (int code : {ROM_E_INVAL, ROM_E_WORKSPACE, ROM_E_UNSUPPORTED, ROM_E_HIP, ROM_E_STATIC_LIMIT, -99})

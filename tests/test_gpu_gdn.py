@@ -78,6 +78,14 @@ def test_gdn_layer_matches_oracle(name, overrides):
     compare_gdn(cfg, gpu, x_np, w_np)
 
 
+def test_gdn_full_size_matches_oracle():
+    """d_model 2048, 32 heads of 64 + 64 channels, 8 experts top-1, as 8 sequences of 2048 tokens (the
+    launch configuration the benchmark times; the oracle steps through 2048 steps)."""
+    cfg = get_gdn_config("gdn_cfg2", batch=8, seq_len=2048, cfg_id=59)
+    gpu, x_np, w_np = run_gdn(cfg)
+    compare_gdn(cfg, gpu, x_np, w_np)
+
+
 def test_gdn_strong_writes_and_decay():
     """beta near 1 and log decays a decade above the default recipe's for some heads, near zero for
     others: the triangular system is far from the identity and the decay factors span their range."""
