@@ -1063,7 +1063,7 @@ namespace {
 struct GdnPlan {              // byte offsets inside the workspace
   size_t total;
   size_t expert_idx, gate, counts, offsets, perm, inv_perm, tok_of_pos, block_counts, logits;
-  size_t proj, proj_sorted, qkv, y, op_sorted, conv_tmp;
+  size_t proj, proj_sorted, qkv, y, op_sorted, conv_tmp, carry;
 };
 
 int check_gdn_dims(const rom_gdn_dims *d) {
@@ -1104,6 +1104,7 @@ GdnPlan make_gdn_plan(const rom_gdn_dims *d, int64_t n_seq, int64_t seq_len) {
   p.y = take(N * Dv * 2);
   p.op_sorted = K > 1 ? take(S * Dm * 2) : kNone;
   p.conv_tmp = take(seq_len > kConvInPlaceMaxLen ? static_cast<size_t>(n_seq) * Dc * 3 * 4 : 0);
+  p.carry = take(gdn_carry_bytes(n_seq, seq_len, d->n_heads, d->d_k));
   p.total = off;
   return p;
 }
@@ -1218,7 +1219,7 @@ int rom_gdn_forward(const rom_gdn_dims *d, const rom_gdn_weights *w, const void 
   // delta rule, head norm, SiLU(z) gate
   mark.begin(ROM_STAGE_SCAN, s);
   ROM_TRY(launch_gdn_scan(at(p.qkv), Dc, 0, Dk, 2 * Dk, at(p.proj), Dp, Dv + Dc, Dv + Dc + H, w->dt_bias, w->A_log, w->norm_w,
-                          eps, B, L, H, d->d_k, ssm_in, ssm_out, at(p.y), Dv, s));
+                          eps, B, L, H, d->d_k, ssm_in, ssm_out, reinterpret_cast<float *>(at(p.carry)), at(p.y), Dv, s));
   mark.end(ROM_STAGE_SCAN, s);
 
   // output projection and the gate-weighted combine

@@ -188,12 +188,13 @@ hipError_t launch_rms_rows(const void *in, const float *w, float eps, int64_t n_
 //   qkv bf16 [B*L, ld_qkv] after conv + SiLU: q of head h at q_col + d_k h, k at k_col + d_k h, v at v_col + 64 h;
 //   proj bf16 [B*L, ld_p]: z of head h at columns 64 h, the beta logit at b_col + h, the decay logit at a_col + h;
 //   dt_bias, A_log f32 [n_heads]; norm_w f32 [64]; s_in / s_out f32 [B, n_heads, d_k, 64] or NULL;
-//   y bf16 [B*L, ld_y]
+//   y bf16 [B*L, ld_y]; carry: f32 scratch of gdn_carry_bytes() (segment carries of long, few sequences)
 bool gdn_supported(int d_k, int d_v);
+size_t gdn_carry_bytes(int64_t B, int64_t L, int n_heads, int d_k);
 hipError_t launch_gdn_scan(const void *qkv, int64_t ld_qkv, int q_col, int k_col, int v_col, const void *proj, int64_t ld_p,
                            int b_col, int a_col, const float *dt_bias, const float *A_log, const float *norm_w, float eps,
-                           int64_t B, int64_t L, int n_heads, int d_k, const float *s_in, float *s_out, void *y,
-                           int64_t ld_y, hipStream_t s);
+                           int64_t B, int64_t L, int n_heads, int d_k, const float *s_in, float *s_out, float *carry,
+                           void *y, int64_t ld_y, hipStream_t s);
 
 // timing probes (bench.py --probe): out is f32 scratch of n_blocks * 256 floats
 hipError_t launch_probe_issue(int op, int chains, int n_blocks, int iters, float *out, hipStream_t s);

@@ -70,7 +70,8 @@ def compare_gdn(cfg, gpu, x_np, w_np, conv_state=None, ssm_state=None):
     ("gdn_small", dict(seq_len=1, batch=3, cfg_id=53)),
     ("gdn_small", dict(seq_len=64, batch=1, cfg_id=54, top_k=4, gate_mode=1)),
     ("gdn_mid", {}),                                                         # top-2, 24 chunks
-    ("gdn_mid", dict(batch=3, seq_len=700, d_k=128, cfg_id=55, top_k=1, gate_mode=0)),
+    ("gdn_mid", dict(batch=3, seq_len=700, d_k=128, cfg_id=55, top_k=1, gate_mode=0)),      # two segments, d_k 128
+    ("gdn_mid", dict(batch=1, seq_len=5003, d_model=256, n_heads=8, cfg_id=62, top_k=1, gate_mode=0)),   # 19 segments
 ])
 def test_gdn_layer_matches_oracle(name, overrides):
     cfg = get_gdn_config(name, **overrides)
@@ -82,6 +83,13 @@ def test_gdn_full_size_matches_oracle():
     """d_model 2048, 32 heads of 64 + 64 channels, 8 experts top-1, as 8 sequences of 2048 tokens (the
     launch configuration the benchmark times; the oracle steps through 2048 steps)."""
     cfg = get_gdn_config("gdn_cfg2", batch=8, seq_len=2048, cfg_id=59)
+    gpu, x_np, w_np = run_gdn(cfg)
+    compare_gdn(cfg, gpu, x_np, w_np)
+
+
+def test_gdn_full_size_one_sequence_matches_oracle():
+    """The same layer on one sequence of 16384 tokens: eight segments per head, the carry pass and the fold."""
+    cfg = get_gdn_config("gdn_cfg2")
     gpu, x_np, w_np = run_gdn(cfg)
     compare_gdn(cfg, gpu, x_np, w_np)
 
@@ -101,8 +109,12 @@ def test_gdn_strong_writes_and_decay():
     compare_gdn(cfg, gpu, x_np, w_np)
 
 
-def test_gdn_states_in_and_out():
-    cfg = get_gdn_config("gdn_small", cfg_id=57, seq_len=300)
+@pytest.mark.parametrize("name,overrides", [
+    ("gdn_small", dict(cfg_id=57, seq_len=300)),                      # one segment
+    ("gdn_mid", dict(cfg_id=61, batch=1, seq_len=1100)),              # four segments: the given state enters the fold
+])
+def test_gdn_states_in_and_out(name, overrides):
+    cfg = get_gdn_config(name, **overrides)
     rng = np.random.default_rng(57)
     cs = rng.standard_normal((cfg.batch, cfg.d_conv_ch, 3)).astype(np.float32)
     ss = (0.3 * rng.standard_normal((cfg.batch, cfg.n_heads, cfg.d_k, cfg.d_v))).astype(np.float32)
