@@ -77,6 +77,11 @@ __device__ __forceinline__ float wave_inclusive_sum(float v) {
   return v;
 }
 
+__device__ __forceinline__ int opaque(int v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
+
 __device__ __forceinline__ float bf16_elem(const u32x4_t &v, int m) {
   const unsigned int w = v[m >> 1];
   return __uint_as_float((m & 1) ? (w & 0xFFFF0000u) : (w << 16));
@@ -98,17 +103,28 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
-// eight 16-byte pieces (8 columns of 8 steps), step i scaled by f[i] -> column-major 16-byte segments
+// eight packed bf16 values times f
+__device__ __forceinline__ u32x4_t scale8(const u32x4_t &v, float f) {
+  u32x4_t o;
+#pragma unroll
+  for (int a = 0; a < 4; ++a) o[a] = pack_bf16x2(f * bf16_elem(v, 2 * a), f * bf16_elem(v, 2 * a + 1));
+  return o;
+}
+// eight 16-byte pieces (8 columns of 8 steps) -> column-major 16-byte segments: word a of column m's
+// segment holds steps 2a, 2a+1, which v_perm_b32 picks out of word m/2 of the two step rows
 template <int PITCH>
-__device__ __forceinline__ void park_scaled_8x8(const u32x4_t (&v)[8], const float (&f)[8], bf16_t (*dst)[PITCH], int col0,
-                                                int step0) {
+__device__ __forceinline__ void park_8x8(const u32x4_t (&v)[8], bf16_t (*dst)[PITCH], int col0, int step0) {
 #pragma unroll
-  for (int m = 0; m < 8; ++m) {
-    u32x4_t seg;
+  for (int w = 0; w < 4; ++w) {          // word w of a piece = columns 2w, 2w+1
+    u32x4_t lo, hi;
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
-      seg[a] = pack_bf16x2(f[2 * a] * bf16_elem(v[2 * a], m), f[2 * a + 1] * bf16_elem(v[2 * a + 1], m));
-    *reinterpret_cast<u32x4_t *>(&dst[col0 + m][step0]) = seg;
+    for (int a = 0; a < 4; ++a) {
+      const unsigned int p0 = v[2 * a][w], p1 = v[2 * a + 1][w];
+      lo[a] = __builtin_amdgcn_perm(p1, p0, 0x05040100u);      // (p0.lo16, p1.lo16)
+      hi[a] = __builtin_amdgcn_perm(p1, p0, 0x07060302u);      // (p0.hi16, p1.hi16)
+    }
+    *reinterpret_cast<u32x4_t *>(&dst[col0 + 2 * w][step0]) = lo;
+    *reinterpret_cast<u32x4_t *>(&dst[col0 + 2 * w + 1][step0]) = hi;
   }
 }
 
@@ -145,6 +161,8 @@ __device__ __forceinline__ void invert_unit_lower(const float (*am)[kQ + 4], flo
 #pragma unroll
       for (int m = 0; m < r; ++m) acc = fmaf(-am[16 * g + r][16 * g + m], x[m], acc);
       x[r] = acc;
+      asm volatile("" ::: "memory");         // row by row: hoisting all 120 LDS reads costs as many registers
+      __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -290,6 +308,10 @@ __global__ __launch_bounds__(256, 1) void gdn_kernel(const bf16_t *__restrict__ 
   fetch_out(ts);
 
   for (int64_t t0 = ts; t0 < te; t0 += kQ) {
+    // The lane's coordinates go through an opaque copy every chunk: with them loop-invariant the compiler
+    // hoists some two hundred addresses and mask predicates out of the loop and spills them.
+    const int gq = opaque(g), cq = opaque(c);
+    const int soq = opaque(so), coq = opaque(co), sopq = soq ^ (coq & 7), erq = opaque(e_row), epq = opaque(e_po);
     // per step: beta, log decay, cumulative log decay (every wavefront for itself, one step per lane)
     float beta = 0.0f, gl = 0.0f;
     if (t0 + lane < te) {
@@ -303,27 +325,23 @@ __global__ __launch_bounds__(256, 1) void gdn_kernel(const bf16_t *__restrict__ 
     if (is_k || is_v) {
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        if (t0 + 8 * so + i >= te) pv[i] = u32x4_t{0u, 0u, 0u, 0u};
+        if (t0 + 8 * soq + i >= te) pv[i] = u32x4_t{0u, 0u, 0u, 0u};
       if (is_k) {
-        // row norms: the n_co lanes with this `so` hold the eight steps' other column blocks
+        // row norms: the n_co lanes with this `soq` hold the eight steps' other column blocks
         const float w_lane = fast_exp2((cum_last - cum) * kLog2e);
-        float rk[8], f[8];
+        // a row at a time (normalised copy out, decay-weighted copy kept packed), then the packed rows are
+        // transposed by byte permutes: few values live at once
+        u32x4_t kw[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          rk[i] = rsqrtf(group_sum<NS / 8>(sum_sq8(pv[i])) + kL2Eps);
-          f[i] = rk[i] * __shfl(w_lane, 8 * so + i);
+          const float rk = rsqrtf(group_sum<NS / 8>(sum_sq8(pv[i])) + kL2Eps);
+          *reinterpret_cast<u32x4_t *>(&sm.u.in.kn[8 * soq + i][8 * coq]) = scale8(pv[i], rk);
+          kw[i] = scale8(pv[i], rk * __shfl(w_lane, 8 * soq + i));
         }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          u32x4_t kv;
-#pragma unroll
-          for (int a = 0; a < 4; ++a) kv[a] = pack_bf16x2(rk[i] * bf16_elem(pv[i], 2 * a), rk[i] * bf16_elem(pv[i], 2 * a + 1));
-          *reinterpret_cast<u32x4_t *>(&sm.u.in.kn[8 * so + i][8 * co]) = kv;
-        }
-        park_scaled_8x8<kQ + 8>(pv, f, sm.kw_t, 8 * co, 8 * so_phys);
+        park_8x8<kQ + 8>(kw, sm.kw_t, 8 * coq, 8 * sopq);
       } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t *>(&sm.vt[8 * so + i][8 * co]) = pv[i];
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t *>(&sm.vt[8 * soq + i][8 * coq]) = pv[i];
       }
     }
     if (!CARRY) {
@@ -346,39 +364,39 @@ __global__ __launch_bounds__(256, 1) void gdn_kernel(const bf16_t *__restrict__ 
     __syncthreads();
     fetch_main(t0 + kQ);
 
-    // ---- scores of this wavefront's 16 steps t = 16 wave + c against all s (computed transposed),
+    // ---- scores of this wavefront's 16 steps t = 16 wave + cq against all s (computed transposed),
     //      and the two products with the state the chunk starts from
     {
-      const float cum_t = sm.cum[16 * wave + c], beta_t = sm.beta[16 * wave + c];
+      const float cum_t = sm.cum[16 * wave + cq], beta_t = sm.beta[16 * wave + cq];
 #pragma unroll
       for (int sb = 0; sb < 4; ++sb) {
         f32x4_t kk = {0.0f, 0.0f, 0.0f, 0.0f}, qk = {0.0f, 0.0f, 0.0f, 0.0f};
         if (sb <= wave) {
 #pragma unroll
           for (int ks = 0; ks < kKS; ++ks) {
-            const bf16x8_t fa = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.u.in.kn[16 * sb + c][32 * ks + 8 * g]));
-            const bf16x8_t fk = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.u.in.kn[16 * wave + c][32 * ks + 8 * g]));
+            const bf16x8_t fa = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.u.in.kn[16 * sb + cq][32 * ks + 8 * gq]));
+            const bf16x8_t fk = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.u.in.kn[16 * wave + cq][32 * ks + 8 * gq]));
             kk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fk, kk, 0, 0, 0);
             if (!CARRY) {
-              const bf16x8_t fq = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.u.in.qr[16 * wave + c][32 * ks + 8 * g]));
+              const bf16x8_t fq = as_frag(*reinterpret_cast<const u32x4_t *>(&sm.u.in.qr[16 * wave + cq][32 * ks + 8 * gq]));
               qk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fq, qk, 0, 0, 0);
             }
           }
         }
-        const f32x4_t cum_s = *reinterpret_cast<const f32x4_t *>(&sm.cum[16 * sb + 4 * g]);
+        const f32x4_t cum_s = *reinterpret_cast<const f32x4_t *>(&sm.cum[16 * sb + 4 * gq]);
         f32x4_t av;
         float gv[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const int s = 16 * sb + 4 * g + r, t = 16 * wave + c;
+          const int s = 16 * sb + 4 * gq + r, t = 16 * wave + cq;
           const float dec = s <= t ? fast_exp2((cum_t - cum_s[r]) * kLog2e) : 0.0f;
           av[r] = s < t ? beta_t * dec * kk[r] : 0.0f;
           gv[r] = dec * qk[r];
         }
-        *reinterpret_cast<f32x4_t *>(&sm.a.am[16 * wave + c][16 * sb + 4 * g]) = av;
+        *reinterpret_cast<f32x4_t *>(&sm.a.am[16 * wave + cq][16 * sb + 4 * gq]) = av;
         if (!CARRY) {
           const u32x2_t packed = {pack_bf16x2(gv[0], gv[1]), pack_bf16x2(gv[2], gv[3])};
-          *reinterpret_cast<u32x2_t *>(&sm.gs[16 * wave + c][16 * sb + 4 * g]) = packed;
+          *reinterpret_cast<u32x2_t *>(&sm.gs[16 * wave + cq][16 * sb + 4 * gq]) = packed;
         }
       }
     }
@@ -396,18 +414,18 @@ __global__ __launch_bounds__(256, 1) void gdn_kernel(const bf16_t *__restrict__ 
       oacc[tb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
       for (int ks = 0; ks < kKS; ++ks) {
-        const bf16x8_t fk = frag_perm<NS + 8>(sm.u.in.kn, 16 * tb + c, 32 * ks, g);
+        const bf16x8_t fk = frag_perm<NS + 8>(sm.u.in.kn, 16 * tb + cq, 32 * ks, gq);
 #pragma unroll
         for (int grp = 0; grp < kG; ++grp) pacc[grp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fk, sop[grp][ks], pacc[grp], 0, 0, 0);
         if (!CARRY)
-          oacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag_perm<NS + 8>(sm.u.in.qr, 16 * tb + c, 32 * ks, g), sop[0][ks],
+          oacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag_perm<NS + 8>(sm.u.in.qr, 16 * tb + cq, 32 * ks, gq), sop[0][ks],
                                                              oacc[tb], 0, 0, 0);
       }
-      const f32x4_t e = *reinterpret_cast<const f32x4_t *>(&sm.ecum[16 * tb + 4 * g]);
-      const f32x4_t bt = *reinterpret_cast<const f32x4_t *>(&sm.beta[16 * tb + 4 * g]);
+      const f32x4_t e = *reinterpret_cast<const f32x4_t *>(&sm.ecum[16 * tb + 4 * gq]);
+      const f32x4_t bt = *reinterpret_cast<const f32x4_t *>(&sm.beta[16 * tb + 4 * gq]);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float vv = bf16_to_f32(sm.vt[16 * tb + 4 * g + r][16 * wave + c]);
+        const float vv = bf16_to_f32(sm.vt[16 * tb + 4 * gq + r][16 * wave + cq]);
         rhs[0][tb][r] = bt[r] * (vv - e[r] * pacc[0][r]);    // beta_t (v_t - gamma_t S_0 k_t)
 #pragma unroll
         for (int grp = 1; grp < kG; ++grp) rhs[grp][tb][r] = -bt[r] * e[r] * pacc[grp][r];      // the same with v = 0
@@ -416,7 +434,7 @@ __global__ __launch_bounds__(256, 1) void gdn_kernel(const bf16_t *__restrict__ 
     }
     __syncthreads();                // A is complete; the step-major keys and queries are no longer read
 
-    invert_unit_lower(sm.a.am, sm.u.tm, sm.tb, lane, wave);
+    invert_unit_lower(sm.a.am, sm.u.tm, sm.tb, opaque(lane), wave);
 
     // ---- U = T rhs (rows t, this wavefront's 16 value channels); the contraction runs over steps,
     //      with rhs taken from the accumulators
@@ -434,7 +452,7 @@ __global__ __launch_bounds__(256, 1) void gdn_kernel(const bf16_t *__restrict__ 
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2)
           if (k2 == 0 || tb >= 2) {
-            const bf16x8_t ft = frag_perm<kQ + 8>(sm.tb, 16 * tb + c, 32 * k2, g);
+            const bf16x8_t ft = frag_perm<kQ + 8>(sm.tb, 16 * tb + cq, 32 * k2, gq);
 #pragma unroll
             for (int grp = 0; grp < kG; ++grp)
               uacc[grp][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ft, rop[grp][k2], uacc[grp][tb], 0, 0, 0);
@@ -453,7 +471,7 @@ __global__ __launch_bounds__(256, 1) void gdn_kernel(const bf16_t *__restrict__ 
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2)
           if (k2 == 0 || tb >= 2)
-            oacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag_perm<kQ + 8>(sm.gs, 16 * tb + c, 32 * k2, g), uop[0][k2],
+            oacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag_perm<kQ + 8>(sm.gs, 16 * tb + cq, 32 * k2, gq), uop[0][k2],
                                                                oacc[tb], 0, 0, 0);
     }
     // state at the chunk's end: S^T = gamma_64 S^T + sum_s (exp(cum_64 - cum_s) k_s) u_s^T
@@ -465,13 +483,13 @@ __global__ __launch_bounds__(256, 1) void gdn_kernel(const bf16_t *__restrict__ 
         for (int grp = 0; grp < kG; ++grp)
 #pragma unroll
           for (int r = 0; r < 4; ++r) sacc[grp][nb][r] *= dec;
-        const int row = 16 * nb + c, sw = (row >> 3) & 7;
+        const int row = 16 * nb + cq, sw = (row >> 3) & 7;
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2) {
-          // steps 32 k2 + 4 g .. +3 and 32 k2 + 16 + 4 g .. +3 of the swizzled channel-major array
-          const int p_lo = (4 * k2 + (g >> 1)) ^ sw, p_hi = (4 * k2 + 2 + (g >> 1)) ^ sw;
-          const u32x2_t lo = *reinterpret_cast<const u32x2_t *>(&sm.kw_t[row][8 * p_lo + 4 * (g & 1)]);
-          const u32x2_t hi = *reinterpret_cast<const u32x2_t *>(&sm.kw_t[row][8 * p_hi + 4 * (g & 1)]);
+          // steps 32 k2 + 4 gq .. +3 and 32 k2 + 16 + 4 gq .. +3 of the swizzled channel-major array
+          const int p_lo = (4 * k2 + (gq >> 1)) ^ sw, p_hi = (4 * k2 + 2 + (gq >> 1)) ^ sw;
+          const u32x2_t lo = *reinterpret_cast<const u32x2_t *>(&sm.kw_t[row][8 * p_lo + 4 * (gq & 1)]);
+          const u32x2_t hi = *reinterpret_cast<const u32x2_t *>(&sm.kw_t[row][8 * p_hi + 4 * (gq & 1)]);
           const bf16x8_t fw = frag_from_halves(lo, hi);
 #pragma unroll
           for (int grp = 0; grp < kG; ++grp)
@@ -483,30 +501,30 @@ __global__ __launch_bounds__(256, 1) void gdn_kernel(const bf16_t *__restrict__ 
     // ---- output rows: query norm and scale, RMS norm over the head's 64 channels, SiLU(z) gate
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb) {
-      const f32x4_t rq = *reinterpret_cast<const f32x4_t *>(&sm.rq[16 * tb + 4 * g]);
+      const f32x4_t rq = *reinterpret_cast<const f32x4_t *>(&sm.rq[16 * tb + 4 * gq]);
 #pragma unroll
-      for (int r = 0; r < 4; ++r) sm.a.y[16 * tb + 4 * g + r][16 * wave + c] = oacc[tb][r] * rq[r];
+      for (int r = 0; r < 4; ++r) sm.a.y[16 * tb + 4 * gq + r][16 * wave + cq] = oacc[tb][r] * rq[r];
     }
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const int row = e_row + 32 * i;
+      const int row = erq + 32 * i;
       const int64_t t = t0 + row;
-      const f32x4_t y0 = *reinterpret_cast<const f32x4_t *>(&sm.a.y[row][8 * e_po]);
-      const f32x4_t y1 = *reinterpret_cast<const f32x4_t *>(&sm.a.y[row][8 * e_po + 4]);
+      const f32x4_t y0 = *reinterpret_cast<const f32x4_t *>(&sm.a.y[row][8 * epq]);
+      const f32x4_t y1 = *reinterpret_cast<const f32x4_t *>(&sm.a.y[row][8 * epq + 4]);
       float ss = 0.0f;
 #pragma unroll
       for (int m = 0; m < 4; ++m) ss = fmaf(y0[m], y0[m], fmaf(y1[m], y1[m], ss));
       const float rstd = rsqrtf(group_sum<8>(ss) * (1.0f / kV) + eps);
       const u32x4_t zv = ez[i];
-      const f32x4_t w0 = *reinterpret_cast<const f32x4_t *>(norm_w + 8 * e_po);
-      const f32x4_t w1 = *reinterpret_cast<const f32x4_t *>(norm_w + 8 * e_po + 4);
+      const f32x4_t w0 = *reinterpret_cast<const f32x4_t *>(norm_w + 8 * epq);
+      const f32x4_t w1 = *reinterpret_cast<const f32x4_t *>(norm_w + 8 * epq + 4);
       float o[8];
 #pragma unroll
       for (int m = 0; m < 8; ++m)
         o[m] = (m < 4 ? y0[m & 3] * w0[m & 3] : y1[m & 3] * w1[m & 3]) * rstd * silu_f32(bf16_elem(zv, m));
       const u32x4_t ov = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])};
-      if (t < te) *reinterpret_cast<u32x4_t *>(y + (b * L + t) * ld_y + h * kV + 8 * e_po) = ov;
+      if (t < te) *reinterpret_cast<u32x4_t *>(y + (b * L + t) * ld_y + h * kV + 8 * epq) = ov;
     }
     fetch_out(t0 + kQ);
   }
