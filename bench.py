@@ -519,6 +519,29 @@ def gdn_rate(steps, warmup):
         out[label] = {"workload": f"{cfg.name}: B={cfg.batch}, L={cfg.seq_len}, d_model={cfg.d_model}, heads={cfg.n_heads}, "
                                   f"d_k={cfg.d_k}, d_v={cfg.d_v}, E={cfg.n_experts}, top_k={cfg.top_k}, bf16",
                       "ms_per_call": ms, "tokens_per_s": cfg.n_tokens / (ms * 1e-3), "stages_ms": stages}
+        if label == "eight_sequences":
+            # the recurrent form: one new token for each of 256 sequences, states updated in place
+            n_seq = 256
+            xs = layer.to_device(make_gdn_input(cfg)[0, :n_seq].copy())
+            cs_shape, ss_shape = layer.state_shapes(n_seq)
+            cs = torch.zeros(cs_shape, device="cuda:0")
+            ss = torch.zeros(ss_shape, device="cuda:0")
+            out_step = torch.empty_like(xs)
+            for _ in range(10):
+                layer.step(xs, cs, ss, out=out_step)
+            torch.cuda.synchronize()
+            evs[0].record()
+            for _ in range(50):
+                layer.step(xs, cs, ss, out=out_step)
+            evs[1].record()
+            torch.cuda.synchronize()
+            ms_step = evs[0].elapsed_time(evs[1]) / 50
+            w_bytes = 2.0 * cfg.n_experts * (cfg.d_in_proj * cfg.d_model + cfg.d_model * cfg.d_vt)
+            s_bytes = 2.0 * 4.0 * n_seq * cfg.n_heads * cfg.d_k * cfg.d_v
+            out["decode_step"] = {"workload": f"rom_gdn_step, {n_seq} sequences", "ms_per_step": ms_step,
+                                  "tokens_per_s": n_seq / (ms_step * 1e-3), "bound": "hbm",
+                                  "algorithmic_gbytes_per_s": (w_bytes + s_bytes) / (ms_step * 1e-3) / 1e9,
+                                  "frac": (w_bytes + s_bytes) / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS}
         del layer, x
     return out
 

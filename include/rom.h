@@ -534,6 +534,13 @@ ROM_API int rom_gdn_forward(const rom_gdn_dims *dims, const rom_gdn_weights *w, 
                             void *out, float *conv_state_out, float *ssm_state_out, void *ws,
                             size_t ws_bytes, void *hip_stream);
 
+/* One new token for each of B sequences (the recurrent form of rom_gdn_forward): x, out T [B, d_model];
+ * conv_state and ssm_state (layouts above, both required) are read and updated in place.
+ *   ws   rom_gdn_workspace_bytes(dims, B, 1) */
+ROM_API int rom_gdn_step(const rom_gdn_dims *dims, const rom_gdn_weights *w, const void *x, int64_t B, float eps,
+                         float *conv_state, float *ssm_state, void *out, void *ws, size_t ws_bytes,
+                         void *hip_stream);
+
 /* Static description of an error code. */
 ROM_API const char *rom_strerror(int code);
 

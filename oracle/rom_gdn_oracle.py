@@ -119,3 +119,11 @@ def rom_gdn_forward(x, w: Dict[str, Optional[np.ndarray]], top_k: int, gate_mode
         "g": g.reshape(n_tok, n_heads), "o": o.reshape(n_tok, d_vt), "y": y,
         "out": out.reshape(bsz, length, d_m), "conv_state": conv_out, "ssm_state": state,
     }
+
+
+def rom_gdn_step(x, w, top_k, gate_mode, n_heads, d_k, conv_state, ssm_state, eps=1e-5, expert_idx=None):
+    """One new token per sequence: x [B, d_model]; the same dict with out [B, d_model] and the updated states."""
+    res = rom_gdn_forward(np.asarray(x, F64)[:, None, :], w, top_k, gate_mode, n_heads, d_k, eps, expert_idx,
+                          conv_state, ssm_state)
+    res["out"] = res["out"][:, 0, :]
+    return res

@@ -161,6 +161,8 @@ def load_library() -> ctypes.CDLL:
     lib.rom_gdn_forward.restype = ctypes.c_int
     lib.rom_gdn_forward.argtypes = [ctypes.POINTER(RomGdnDims), ctypes.POINTER(_RomGdnWeights), P, I64, I64, F32, P, P,
                                     P, P, P, P, SZ, P]
+    lib.rom_gdn_step.restype = ctypes.c_int
+    lib.rom_gdn_step.argtypes = [ctypes.POINTER(RomGdnDims), ctypes.POINTER(_RomGdnWeights), P, I64, F32, P, P, P, P, SZ, P]
     lib.rom_strerror.restype = ctypes.c_char_p
     lib.rom_strerror.argtypes = [ctypes.c_int]
     lib.rom_profile_enable.restype = ctypes.c_int
@@ -400,10 +402,22 @@ def rom_gdn_workspace_layout(dims: RomGdnDims, B: int, L: int) -> Dict[str, int]
     return {n: int(getattr(lay, n)) for n, _ in _RomGdnWsLayout._fields_}
 
 
-def rom_gdn_forward(dims, weights, x, B, L, eps, conv_state_in, ssm_state_in, out, conv_state_out, ssm_state_out, ws):
-    wstruct = _RomGdnWeights()
+def _gdn_weights_struct(weights) -> _RomGdnWeights:
+    s = _RomGdnWeights()
     for name, _ in _RomGdnWeights._fields_:
-        setattr(wstruct, name, _ptr(weights.get(name)))
+        setattr(s, name, _ptr(weights.get(name)))
+    return s
+
+
+def rom_gdn_step(dims, weights, x, B, eps, conv_state, ssm_state, out, ws):
+    code = load_library().rom_gdn_step(
+        ctypes.byref(dims), ctypes.byref(_gdn_weights_struct(weights)), _ptr(x), B, eps, _ptr(conv_state), _ptr(ssm_state),
+        _ptr(out), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check(code, "rom_gdn_step")
+
+
+def rom_gdn_forward(dims, weights, x, B, L, eps, conv_state_in, ssm_state_in, out, conv_state_out, ssm_state_out, ws):
+    wstruct = _gdn_weights_struct(weights)
     code = load_library().rom_gdn_forward(
         ctypes.byref(dims), ctypes.byref(wstruct), _ptr(x), B, L, eps, _ptr(conv_state_in), _ptr(ssm_state_in), _ptr(out),
         _ptr(conv_state_out), _ptr(ssm_state_out), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
@@ -915,3 +929,10 @@ class RomGdnLayer:
         rom_gdn_forward(self.dims, self.weights, x, B, L, self.eps, conv_state, ssm_state, out, conv_out, ssm_out,
                         self.workspace(max(B, 1), max(L, 1)))
         return (out, conv_out, ssm_out) if return_states else out
+
+    def step(self, x: torch.Tensor, conv_state: torch.Tensor, ssm_state: torch.Tensor, out=None) -> torch.Tensor:
+        """x [B, d_model]; the states are updated in place."""
+        B = int(x.shape[0])
+        out = torch.empty_like(x) if out is None else out
+        rom_gdn_step(self.dims, self.weights, x, B, self.eps, conv_state, ssm_state, out, self.workspace(max(B, 1), 1))
+        return out

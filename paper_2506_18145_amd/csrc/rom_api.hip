@@ -1244,6 +1244,12 @@ int rom_gdn_forward(const rom_gdn_dims *d, const rom_gdn_weights *w, const void 
   return ROM_OK;
 }
 
+int rom_gdn_step(const rom_gdn_dims *d, const rom_gdn_weights *w, const void *x, int64_t B, float eps, float *conv_state,
+                 float *ssm_state, void *out, void *ws, size_t ws_bytes, void *hip_stream) {
+  if (B > 0 && (!conv_state || !ssm_state)) return ROM_E_INVAL;
+  return rom_gdn_forward(d, w, x, B, 1, eps, conv_state, ssm_state, out, conv_state, ssm_state, ws, ws_bytes, hip_stream);
+}
+
 size_t rom_backward_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L) {
   if (check_dims(dims) != ROM_OK || B < 0 || L < 0) return 0;
   return make_bwd_plan(dims, B > 0 ? B : 1, L > 0 ? L : 1).total;

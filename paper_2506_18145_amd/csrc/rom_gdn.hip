@@ -585,6 +585,80 @@ __global__ __launch_bounds__(256) void gdn_fold_kernel(const float *__restrict__
   }
 }
 
+// One step per sequence (L == 1): grid (n_heads, B); thread = (value channel v, quarter of the key channels).
+// The state is read and written once, in rows of 64 consecutive value channels.
+template <int NS>
+__global__ __launch_bounds__(256) void gdn_step_kernel(const bf16_t *__restrict__ qkv, int64_t ld_qkv, int q_col, int k_col,
+                                                       int v_col, const bf16_t *__restrict__ proj, int64_t ld_p, int b_col,
+                                                       int a_col, const float *__restrict__ dt_bias,
+                                                       const float *__restrict__ A_log, const float *__restrict__ norm_w,
+                                                       float eps, const float *s_in, float *s_out, bf16_t *__restrict__ y,
+                                                       int64_t ld_y) {
+  __shared__ float kq[2][NS];          // normalised key, normalised and scaled query
+  __shared__ float part[4][kV];
+  __shared__ float red[2][4];
+  const int tid = threadIdx.x, v = tid & 63, q4 = tid >> 6, lane = tid & 63;
+  const int h = blockIdx.x, n_heads = gridDim.x;
+  const int64_t b = blockIdx.y;
+  const bf16_t *row = qkv + b * ld_qkv;
+  const bf16_t *prow = proj + b * ld_p;
+  // L2 norms of q and k: threads [0, NS) square a key element, threads [128, 128 + NS) a query element
+  float kval = 0.0f, qval = 0.0f;
+  if (tid < NS) kval = bf16_to_f32(row[k_col + h * NS + tid]);
+  if (tid >= 128 && tid < 128 + NS) qval = bf16_to_f32(row[q_col + h * NS + tid - 128]);
+  float sk = kval * kval, sq = qval * qval;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    sk += __shfl_xor(sk, off);
+    sq += __shfl_xor(sq, off);
+  }
+  if (lane == 0) {
+    red[0][q4] = sk;
+    red[1][q4] = sq;
+  }
+  __syncthreads();
+  const float rk = rsqrtf(red[0][0] + red[0][1] + red[0][2] + red[0][3] + kL2Eps);
+  const float rq = rsqrtf(red[1][0] + red[1][1] + red[1][2] + red[1][3] + kL2Eps) * rsqrtf(static_cast<float>(NS));
+  if (tid < NS) kq[0][tid] = kval * rk;
+  if (tid >= 128 && tid < 128 + NS) kq[1][tid - 128] = qval * rq;
+  __syncthreads();
+  const float beta = fast_rcp(1.0f + __expf(-bf16_to_f32(prow[b_col + h])));
+  const float alpha = __expf(-__expf(A_log[h]) * softplus_f32(bf16_to_f32(prow[a_col + h]) + dt_bias[h]));
+  // this thread's state values: S^T[n][v] for its quarter of n
+  constexpr int kPer = NS / 4;
+  const int64_t base = (b * n_heads + h) * static_cast<int64_t>(NS) * kV + v;
+  float st[kPer];
+  float pred = 0.0f;
+#pragma unroll
+  for (int j = 0; j < kPer; ++j) {
+    const int n = q4 * kPer + j;
+    st[j] = alpha * (s_in ? s_in[base + static_cast<int64_t>(n) * kV] : 0.0f);
+    pred = fmaf(st[j], kq[0][n], pred);
+  }
+  part[q4][v] = pred;
+  __syncthreads();
+  const float u = beta * (bf16_to_f32(row[v_col + h * kV + v]) - (part[0][v] + part[1][v] + part[2][v] + part[3][v]));
+  __syncthreads();
+  float o = 0.0f;
+#pragma unroll
+  for (int j = 0; j < kPer; ++j) {
+    const int n = q4 * kPer + j;
+    st[j] = fmaf(u, kq[0][n], st[j]);
+    if (s_out) s_out[base + static_cast<int64_t>(n) * kV] = st[j];
+    o = fmaf(st[j], kq[1][n], o);
+  }
+  part[q4][v] = o;
+  __syncthreads();
+  if (q4 == 0) {
+    const float ov = part[0][v] + part[1][v] + part[2][v] + part[3][v];
+    float ss = ov * ov;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    const float rstd = rsqrtf(ss * (1.0f / kV) + eps);
+    y[b * ld_y + h * kV + v] = f32_to_bf16(ov * rstd * norm_w[v] * silu_f32(bf16_to_f32(prow[h * kV + v])));
+  }
+}
+
 struct GdnPlanSeg {
   int n_seg;
   int64_t seg_len;
@@ -627,6 +701,12 @@ hipError_t gdn_dispatch(const bf16_t *qkv, int64_t ld_qkv, int q_col, int k_col,
                         int b_col, int a_col, const float *dt_bias, const float *A_log, const float *norm_w, float eps,
                         int64_t B, int64_t L, int n_heads, const float *s_in, float *s_out, float *carry, bf16_t *y,
                         int64_t ld_y, hipStream_t s) {
+  if (L == 1) {
+    hipLaunchKernelGGL((gdn_step_kernel<NS>), dim3(static_cast<unsigned>(n_heads), static_cast<unsigned>(B)), dim3(256), 0,
+                       s, qkv, ld_qkv, q_col, k_col, v_col, proj, ld_p, b_col, a_col, dt_bias, A_log, norm_w, eps, s_in, s_out,
+                       y, ld_y);
+    return hipGetLastError();
+  }
   const GdnPlanSeg p = gdn_plan(B, L, n_heads);
   const size_t units = static_cast<size_t>(B) * n_heads * p.n_seg;
   float *carry_z = carry, *carry_m = carry + units * NS * kV, *s_start = carry_m + units * NS * NS;

@@ -214,6 +214,9 @@ int main() {
     float *st = reinterpret_cast<float *>(addr);
     CHECK(rom_gdn_forward(&m, &gw, addr, 1, 64, 1e-5f, nullptr, st, addr + 4096, nullptr, st, addr, 4096, nullptr) == ROM_E_INVAL);
     CHECK(rom_gdn_forward(&m, &gw, addr, 1, 64, 1e-5f, nullptr, nullptr, addr, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_gdn_step(&m, &gw, addr, 4, 1e-5f, nullptr, st, addr + 4096, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_gdn_step(&m, &gw, addr, 4, 1e-5f, st, st, addr + 4096, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+    CHECK(rom_gdn_step(&m, &gw, addr, 0, 1e-5f, nullptr, nullptr, addr + 4096, addr, 4096, nullptr) == ROM_OK);
   }
 
   // ---- strings and the profiling bookkeeping

@@ -210,6 +210,14 @@ def test_state_carry_equals_unsplit_and_causality():
                                ssm_state=first["ssm_state"])
     np.testing.assert_allclose(np.concatenate([first["out"], second["out"]], axis=1), whole["out"], rtol=1e-9, atol=1e-12)
     np.testing.assert_allclose(second["ssm_state"], whole["ssm_state"], rtol=1e-9, atol=1e-12)
+    # token by token through the step
+    cs = np.zeros((cfg.batch, cfg.d_conv_ch, cfg.d_conv - 1))
+    ss = np.zeros((cfg.batch, cfg.n_heads, cfg.d_v, cfg.d_k))
+    for t in range(cfg.seq_len):
+        res = G.rom_gdn_step(x[:, t], w, 2, 1, cfg.n_heads, cfg.d_k, cs, ss)
+        cs, ss = res["conv_state"], res["ssm_state"]
+        np.testing.assert_allclose(res["out"], whole["out"][:, t], rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(ss, whole["ssm_state"], rtol=1e-9, atol=1e-12)
     x2 = x.copy()
     x2[0, 5:] += 1.0
     moved = G.rom_gdn_forward(x2, w, 2, 1, cfg.n_heads, cfg.d_k)["out"]
