@@ -16,7 +16,7 @@
 // way on the C side).  Sequences are cut into segments until there are two workgroups per CU; a
 // first pass (the same kernel without its output part) leaves every segment's end state from a
 // zero start and its total log decay, which the main pass folds in segment order.
-#include "rom_internal.h"
+#include "rom_chunk.h"
 
 #include <atomic>
 #include <mutex>
@@ -24,16 +24,9 @@
 namespace rom {
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+using namespace chunk;
 
-constexpr int kQ = 64;          // steps per chunk
 constexpr int kP = 64;          // channels per head
-constexpr float kLog2e = 1.44269504088896341f;
-
-__device__ __forceinline__ float softplus_f32(float v) { return v > 20.0f ? v : log1pf(__expf(v)); }
 
 // LDS of one workgroup.  Rows are padded by 8 halfs (16 bytes): the 16-byte fragment reads of 16
 // consecutive rows then fall into different banks.
@@ -49,66 +42,6 @@ struct SsdSmem {
   bf16_t g[kQ][kQ + 8];         // masked, decayed, dt-weighted scores [t][s]
   float cum[kQ], ecum[kQ], dt[kQ];   // cum_t, exp(cum_t), dt_t
 };
-
-// Inclusive prefix sum over the 64 lanes by DPP: shifts inside the rows of 16, then lane 15 of rows
-// 0 / 2 into rows 1 / 3 and lane 31 into rows 2 and 3.  Lanes a shift brings nothing to add zero.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_or_zero(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
-}
-__device__ __forceinline__ float wave_inclusive_sum(float v) {
-  v += dpp_or_zero<0x111, 0xF>(v);      // row_shr:1
-  v += dpp_or_zero<0x112, 0xF>(v);      // row_shr:2
-  v += dpp_or_zero<0x114, 0xF>(v);      // row_shr:4
-  v += dpp_or_zero<0x118, 0xF>(v);      // row_shr:8
-  v += dpp_or_zero<0x142, 0xA>(v);      // row_bcast:15 into rows 1 and 3
-  v += dpp_or_zero<0x143, 0xC>(v);      // row_bcast:31 into rows 2 and 3
-  return v;
-}
-
-__device__ __forceinline__ float bf16_elem(const u32x4_t &v, int m) {      // element m (0..7) of 8 packed bf16
-  const unsigned int w = v[m >> 1];
-  return __uint_as_float((m & 1) ? (w & 0xFFFF0000u) : (w << 16));
-}
-
-// Eight 16-byte pieces (eight consecutive columns of eight consecutive steps), step i scaled by f[i],
-// to LDS column-major: for each of the eight columns the eight steps as one 16-byte row segment.
-template <int PITCH>
-__device__ __forceinline__ void park_scaled_8x8(const u32x4_t (&v)[8], const float (&f)[8], bf16_t (*dst)[PITCH], int col0,
-                                                int step0) {
-#pragma unroll
-  for (int m = 0; m < 8; ++m) {
-    u32x4_t seg;
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-      seg[a] = pack_bf16x2(f[2 * a] * bf16_elem(v[2 * a], m), f[2 * a + 1] * bf16_elem(v[2 * a + 1], m));
-    *reinterpret_cast<u32x4_t *>(&dst[col0 + m][step0]) = seg;
-  }
-}
-
-// The same without scaling: word a of column m's segment holds steps 2a, 2a+1, which v_perm_b32
-// picks out of word m/2 of the two step rows.
-template <int PITCH>
-__device__ __forceinline__ void park_8x8(const u32x4_t (&v)[8], bf16_t (*dst)[PITCH], int col0, int step0) {
-#pragma unroll
-  for (int w = 0; w < 4; ++w) {          // word w of a piece = columns 2w, 2w+1
-    u32x4_t lo, hi;
-#pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      const unsigned int p0 = v[2 * a][w], p1 = v[2 * a + 1][w];
-      lo[a] = __builtin_amdgcn_perm(p1, p0, 0x05040100u);      // (p0.lo16, p1.lo16)
-      hi[a] = __builtin_amdgcn_perm(p1, p0, 0x07060302u);      // (p0.hi16, p1.hi16)
-    }
-    *reinterpret_cast<u32x4_t *>(&dst[col0 + 2 * w][step0]) = lo;
-    *reinterpret_cast<u32x4_t *>(&dst[col0 + 2 * w + 1][step0]) = hi;
-  }
-}
-
-__device__ __forceinline__ bf16x8_t as_frag(const u32x4_t &v) { return __builtin_bit_cast(bf16x8_t, v); }
-__device__ __forceinline__ bf16x8_t frag_from_halves(const u32x2_t &lo, const u32x2_t &hi) {
-  const u32x4_t v = {lo[0], lo[1], hi[0], hi[1]};
-  return __builtin_bit_cast(bf16x8_t, v);
-}
 
 // Grid (n_heads, B * n_seg).  CARRY: the state-only pass (segments before the last one).
 //   xbc   bf16 [B*L, ld_xbc]: x of head h at columns x_col + 64 h, B at b_col, C at c_col (after conv + SiLU)
