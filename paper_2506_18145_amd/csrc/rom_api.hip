@@ -524,6 +524,124 @@ int static_scratch_for_current_device(void **out) {
   return ROM_OK;
 }
 
+// ---------------------------------------------------------------- the frame of the Mamba2 / Gated DeltaNet variants
+// What RoM on the two "streamlined" layers shares (Sec. 5.2): router and grouping, ONE routed input
+// projection whose rows come back in token order, a conv + SiLU over a column range of it, the layer's
+// own sequence kernels, and the routed, gate-weighted output projection.
+struct VariantFrame {
+  int dtype, gate_mode, n_experts, top_k, d_model;
+  int d_proj;                  // columns of the input projection
+  int conv_col, d_conv_ch;     // the conv reads columns [conv_col, conv_col + d_conv_ch) of it
+  int d_y;                     // columns of the output projection's input
+  const void *w_router;
+  const float *b_router;
+  const void *w_in;
+  const float *conv_w, *conv_b;
+  const void *w_out;
+  // byte offsets inside the workspace
+  size_t expert_idx, gate, counts, offsets, perm, inv_perm, tok_of_pos, block_counts, logits;
+  size_t proj, proj_sorted, conv_dst, y, op_sorted, conv_tmp;
+};
+
+// argument checks both variants share (after their own dims / weights checks)
+int check_variant_call(const void *x, const void *out, const void *ws, int64_t B, int64_t L, int top_k, float eps,
+                       const float *conv_in, const float *ssm_in, const float *conv_out, const float *ssm_out) {
+  if (!(eps >= 0.0f)) return ROM_E_INVAL;
+  if (!x || !out || !ws || x == out) return ROM_E_INVAL;
+  if (!aligned16(x) || !aligned16(out) || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return ROM_E_INVAL;
+  if (B * L * top_k > (1ll << 30) || B > 65535) return ROM_E_UNSUPPORTED;
+  const float *states[] = {conv_in, ssm_in, conv_out, ssm_out};
+  for (const float *ptr : states)
+    if (ptr && !aligned16(ptr)) return ROM_E_INVAL;
+  // a sequence longer than one conv run / one chunk is worked on by several workgroups: they would
+  // read the old state while another writes the new one
+  if (L > kConvInPlaceMaxLen && ((conv_in && conv_in == conv_out) || (ssm_in && ssm_in == ssm_out))) return ROM_E_INVAL;
+  return ROM_OK;
+}
+
+// seq(mark): launches the layer's own kernels between the conv and the output projection (they read the
+// projection and the conv output, and leave the output projection's input at f.y); returns a ROM_* code.
+template <typename SeqFn>
+int run_variant(const VariantFrame &f, const void *x, int64_t B, int64_t L, const float *conv_in, float *conv_out,
+                void *out, char *base, hipStream_t s, SeqFn &&seq) {
+  auto at = [&](size_t off) { return base + off; };
+  const int64_t N = B * L, S = N * f.top_k;
+  const bool multi = f.top_k > 1;
+  float *gate = reinterpret_cast<float *>(at(f.gate));
+  int32_t *offsets = reinterpret_cast<int32_t *>(at(f.offsets));
+  int32_t *inv_perm = reinterpret_cast<int32_t *>(at(f.inv_perm));
+  int32_t *tok_of_pos = reinterpret_cast<int32_t *>(at(f.tok_of_pos));
+
+  // the router and the grouping are the Mamba layer's
+  rom_dims rd;
+  memset(&rd, 0, sizeof(rd));
+  rd.d_model = f.d_model; rd.d_inner = f.d_y; rd.n_experts = f.n_experts; rd.top_k = f.top_k;
+  rd.n_experts_xdt = f.n_experts; rd.dtype = f.dtype; rd.gate_mode = f.gate_mode;
+  rom_weights rw;
+  memset(&rw, 0, sizeof(rw));
+  rw.w_router = f.w_router; rw.b_router = f.b_router;
+  StageMark mark;
+  int rc = route_into(&rd, &rw, x, N, reinterpret_cast<int32_t *>(at(f.expert_idx)), gate,
+                      reinterpret_cast<int32_t *>(at(f.counts)), offsets, reinterpret_cast<int32_t *>(at(f.perm)), inv_perm,
+                      tok_of_pos, reinterpret_cast<int32_t *>(at(f.block_counts)), reinterpret_cast<float *>(at(f.logits)),
+                      nullptr, nullptr, s, &mark);
+  if (rc != ROM_OK) return rc;
+
+  // input projection: one routed GEMM, rows back in token order (K > 1: per-slot rows, then their sum)
+  mark.begin(ROM_STAGE_IN_PROJ, s);
+  GemmArgs ga;
+  memset(&ga, 0, sizeof(ga));
+  ga.dtype = f.dtype;
+  ga.A = x; ga.lda = f.d_model; ga.a_rows = tok_of_pos; ga.a_span = N * f.d_model;
+  ga.W = f.w_in; ga.N = f.d_proj; ga.K = f.d_model;
+  ga.n_groups = f.n_experts; ga.M = S; ga.offsets = offsets;
+  ga.C = multi ? at(f.proj_sorted) : at(f.proj); ga.ldc = f.d_proj; ga.c_rows = multi ? nullptr : tok_of_pos;
+  ROM_TRY(launch_grouped_gemm(ga, s));
+  if (multi)
+    ROM_TRY(launch_slot_sum(0, 0, at(f.proj_sorted), f.d_proj, at(f.proj), f.d_proj, inv_perm, N, f.top_k, f.d_proj, nullptr, 0,
+                            nullptr, s));
+  mark.end(ROM_STAGE_IN_PROJ, s);
+
+  // short conv + SiLU, read in place from the projection's output
+  mark.begin(ROM_STAGE_CONV, s);
+  {
+    float *ctmp = reinterpret_cast<float *>(at(f.conv_tmp));
+    const bool beside = conv_out && L > kConvInPlaceMaxLen;
+    ROM_TRY(launch_conv_silu(f.dtype, at(f.proj) + static_cast<size_t>(f.conv_col) * 2, f.d_proj, f.conv_w, f.conv_b, conv_in,
+                             beside ? ctmp : conv_out, at(f.conv_dst), B, L, f.d_conv_ch, s));
+    if (beside) {
+      const int64_t n = B * f.d_conv_ch * 3;
+      hipLaunchKernelGGL(copy_f32_kernel, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, s, ctmp, conv_out, n);
+      ROM_TRY(hipGetLastError());
+    }
+  }
+  mark.end(ROM_STAGE_CONV, s);
+
+  rc = seq(mark);
+  if (rc != ROM_OK) return rc;
+
+  // output projection and the gate-weighted combine
+  mark.begin(ROM_STAGE_OUT_PROJ, s);
+  memset(&ga, 0, sizeof(ga));
+  ga.dtype = f.dtype;
+  ga.A = at(f.y); ga.lda = f.d_y; ga.a_rows = tok_of_pos; ga.a_span = N * f.d_y;
+  ga.W = f.w_out; ga.N = f.d_model; ga.K = f.d_y;
+  ga.n_groups = f.n_experts; ga.M = S; ga.offsets = offsets;
+  if (multi) {
+    ga.C = at(f.op_sorted); ga.ldc = f.d_model;
+    ROM_TRY(launch_grouped_gemm(ga, s));
+    mark.end(ROM_STAGE_OUT_PROJ, s);
+    mark.begin(ROM_STAGE_COMBINE, s);
+    ROM_TRY(launch_combine(f.dtype, at(f.op_sorted), inv_perm, gate, out, N, f.top_k, f.d_model, nullptr, s));
+    mark.end(ROM_STAGE_COMBINE, s);
+  } else {
+    ga.C = out; ga.ldc = f.d_model; ga.c_rows = tok_of_pos; ga.row_scale = gate;
+    ROM_TRY(launch_grouped_gemm(ga, s));
+    mark.end(ROM_STAGE_OUT_PROJ, s);
+  }
+  return ROM_OK;
+}
+
 }  // namespace
 }  // namespace rom
 
@@ -944,111 +1062,38 @@ int rom_mamba2_forward(const rom_mamba2_dims *d, const rom_mamba2_weights *w, co
       if (!ptr || !aligned16(ptr)) return ROM_E_INVAL;
     if ((w->b_router && !aligned16(w->b_router)) || (w->conv_b && !aligned16(w->conv_b))) return ROM_E_INVAL;
   }
-  if (B < 0 || L < 0 || !(eps >= 0.0f)) return ROM_E_INVAL;
+  if (B < 0 || L < 0) return ROM_E_INVAL;
   if (B == 0 || L == 0) return ROM_OK;
-  if (!x || !out || !ws || x == out) return ROM_E_INVAL;
-  if (!aligned16(x) || !aligned16(out) || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return ROM_E_INVAL;
-  if (B * L * d->top_k > (1ll << 30) || B > 65535) return ROM_E_UNSUPPORTED;
-  {
-    const float *states[] = {conv_in, ssm_in, conv_out, ssm_out};
-    for (const float *ptr : states)
-      if (ptr && !aligned16(ptr)) return ROM_E_INVAL;
-    // a sequence longer than one conv run / one chunk is worked on by several workgroups: they would
-    // read the old state while another writes the new one
-    if (L > kConvInPlaceMaxLen && ((conv_in && conv_in == conv_out) || (ssm_in && ssm_in == ssm_out))) return ROM_E_INVAL;
-  }
-  const int64_t N = B * L;
+  rc = check_variant_call(x, out, ws, B, L, d->top_k, eps, conv_in, ssm_in, conv_out, ssm_out);
+  if (rc != ROM_OK) return rc;
   const Mamba2Plan p = make_mamba2_plan(d, B, L);
   if (ws_bytes < p.total) return ROM_E_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-
   char *base = static_cast<char *>(ws);
-  auto at = [&](size_t off) { return base + off; };
-  const int K = d->top_k, E = d->n_experts, De = d->d_inner, Dm = d->d_model, Ns = d->d_state;
-  const int H = De / d->headdim, Dp = 2 * De + 2 * Ns + H, Dc = De + 2 * Ns;
-  const bool multi = K > 1;
-  const int64_t S = N * K;
-  float *gate = reinterpret_cast<float *>(at(p.gate));
-  int32_t *offsets = reinterpret_cast<int32_t *>(at(p.offsets));
-  int32_t *inv_perm = reinterpret_cast<int32_t *>(at(p.inv_perm));
-  int32_t *tok_of_pos = reinterpret_cast<int32_t *>(at(p.tok_of_pos));
+  const int De = d->d_inner, Ns = d->d_state, H = De / d->headdim, Dp = 2 * De + 2 * Ns + H, Dc = De + 2 * Ns;
 
-  // the router and the grouping are the Mamba layer's
-  rom_dims rd;
-  memset(&rd, 0, sizeof(rd));
-  rd.d_model = Dm; rd.d_inner = De; rd.n_experts = E; rd.top_k = K; rd.n_experts_xdt = E;
-  rd.dtype = d->dtype; rd.gate_mode = d->gate_mode;
-  rom_weights rw;
-  memset(&rw, 0, sizeof(rw));
-  rw.w_router = w->w_router; rw.b_router = w->b_router;
-  StageMark mark;
-  rc = route_into(&rd, &rw, x, N, reinterpret_cast<int32_t *>(at(p.expert_idx)), gate,
-                  reinterpret_cast<int32_t *>(at(p.counts)), offsets, reinterpret_cast<int32_t *>(at(p.perm)), inv_perm,
-                  tok_of_pos, reinterpret_cast<int32_t *>(at(p.block_counts)), reinterpret_cast<float *>(at(p.logits)),
-                  nullptr, nullptr, s, &mark);
-  if (rc != ROM_OK) return rc;
-
-  // input projection z | x | B | C | dt: one routed GEMM, rows back in token order
-  mark.begin(ROM_STAGE_IN_PROJ, s);
-  GemmArgs ga;
-  memset(&ga, 0, sizeof(ga));
-  ga.dtype = d->dtype;
-  ga.A = x; ga.lda = Dm; ga.a_rows = tok_of_pos; ga.a_span = N * Dm;
-  ga.W = w->w_in; ga.N = Dp; ga.K = Dm;
-  ga.n_groups = E; ga.M = S; ga.offsets = offsets;
-  ga.C = multi ? at(p.zx_sorted) : at(p.zxbcdt); ga.ldc = Dp; ga.c_rows = multi ? nullptr : tok_of_pos;
-  ROM_TRY(launch_grouped_gemm(ga, s));
-  if (multi)
-    ROM_TRY(launch_slot_sum(0, 0, at(p.zx_sorted), Dp, at(p.zxbcdt), Dp, inv_perm, N, K, Dp, nullptr, 0, nullptr, s));
-  mark.end(ROM_STAGE_IN_PROJ, s);
-
-  // short conv + SiLU over the channels x | B | C
-  mark.begin(ROM_STAGE_CONV, s);
-  {
-    float *ctmp = reinterpret_cast<float *>(at(p.conv_tmp));
-    const bool beside = conv_out && L > kConvInPlaceMaxLen;
-    ROM_TRY(launch_conv_silu(d->dtype, at(p.zxbcdt) + static_cast<size_t>(De) * 2, Dp, w->conv_w, w->conv_b, conv_in,
-                             beside ? ctmp : conv_out, at(p.xbc), B, L, Dc, s));
-    if (beside) {
-      const int64_t n = B * Dc * 3;
-      hipLaunchKernelGGL(copy_f32_kernel, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, s, ctmp, conv_out, n);
-      ROM_TRY(hipGetLastError());
-    }
-  }
-  mark.end(ROM_STAGE_CONV, s);
-
-  // recurrence, D skip, SiLU(z) gate
-  mark.begin(ROM_STAGE_SCAN, s);
-  ROM_TRY(launch_ssd_scan(at(p.xbc), Dc, 0, De, De + Ns, at(p.zxbcdt), Dp, 2 * De + 2 * Ns, at(p.zxbcdt), Dp, w->dt_bias,
-                          w->A_log, w->D, ssm_in, ssm_out, B, L, H, Ns, reinterpret_cast<float *>(at(p.carry)), at(p.yz), De,
-                          s));
-  mark.end(ROM_STAGE_SCAN, s);
-
-  // RMS norm of the gated rows
-  mark.begin(ROM_STAGE_DT_PROJ, s);
-  ROM_TRY(launch_rms_rows(at(p.yz), w->norm_w, eps, N, De, at(p.g), s));
-  mark.end(ROM_STAGE_DT_PROJ, s);
-
-  // output projection and the gate-weighted combine
-  mark.begin(ROM_STAGE_OUT_PROJ, s);
-  memset(&ga, 0, sizeof(ga));
-  ga.dtype = d->dtype;
-  ga.A = at(p.g); ga.lda = De; ga.a_rows = tok_of_pos; ga.a_span = N * De;
-  ga.W = w->w_out; ga.N = Dm; ga.K = De;
-  ga.n_groups = E; ga.M = S; ga.offsets = offsets;
-  if (multi) {
-    ga.C = at(p.op_sorted); ga.ldc = Dm;
-    ROM_TRY(launch_grouped_gemm(ga, s));
-    mark.end(ROM_STAGE_OUT_PROJ, s);
-    mark.begin(ROM_STAGE_COMBINE, s);
-    ROM_TRY(launch_combine(d->dtype, at(p.op_sorted), inv_perm, gate, out, N, K, Dm, nullptr, s));
-    mark.end(ROM_STAGE_COMBINE, s);
-  } else {
-    ga.C = out; ga.ldc = Dm; ga.c_rows = tok_of_pos; ga.row_scale = gate;
-    ROM_TRY(launch_grouped_gemm(ga, s));
-    mark.end(ROM_STAGE_OUT_PROJ, s);
-  }
-  return ROM_OK;
+  VariantFrame f;
+  f.dtype = d->dtype; f.gate_mode = d->gate_mode; f.n_experts = d->n_experts; f.top_k = d->top_k; f.d_model = d->d_model;
+  f.d_proj = Dp; f.conv_col = De; f.d_conv_ch = Dc; f.d_y = De;          // z | x | B | C | dt: the conv runs over x | B | C
+  f.w_router = w->w_router; f.b_router = w->b_router; f.w_in = w->w_in; f.conv_w = w->conv_w; f.conv_b = w->conv_b;
+  f.w_out = w->w_out;
+  f.expert_idx = p.expert_idx; f.gate = p.gate; f.counts = p.counts; f.offsets = p.offsets; f.perm = p.perm;
+  f.inv_perm = p.inv_perm; f.tok_of_pos = p.tok_of_pos; f.block_counts = p.block_counts; f.logits = p.logits;
+  f.proj = p.zxbcdt; f.proj_sorted = p.zx_sorted; f.conv_dst = p.xbc; f.y = p.g; f.op_sorted = p.op_sorted;
+  f.conv_tmp = p.conv_tmp;
+  return run_variant(f, x, B, L, conv_in, conv_out, out, base, s, [&](StageMark &mark) {
+    // recurrence, D skip, SiLU(z) gate
+    mark.begin(ROM_STAGE_SCAN, s);
+    ROM_TRY(launch_ssd_scan(base + p.xbc, Dc, 0, De, De + Ns, base + p.zxbcdt, Dp, 2 * De + 2 * Ns, base + p.zxbcdt, Dp,
+                            w->dt_bias, w->A_log, w->D, ssm_in, ssm_out, B, L, H, Ns, reinterpret_cast<float *>(base + p.carry),
+                            base + p.yz, De, s));
+    mark.end(ROM_STAGE_SCAN, s);
+    // RMS norm of the gated rows
+    mark.begin(ROM_STAGE_DT_PROJ, s);
+    ROM_TRY(launch_rms_rows(base + p.yz, w->norm_w, eps, B * L, De, base + p.g, s));
+    mark.end(ROM_STAGE_DT_PROJ, s);
+    return static_cast<int>(ROM_OK);
+  });
 }
 
 int rom_mamba2_step(const rom_mamba2_dims *d, const rom_mamba2_weights *w, const void *x, int64_t B, float eps,
@@ -1146,102 +1191,34 @@ int rom_gdn_forward(const rom_gdn_dims *d, const rom_gdn_weights *w, const void 
       if (!ptr || !aligned16(ptr)) return ROM_E_INVAL;
     if ((w->b_router && !aligned16(w->b_router)) || (w->conv_b && !aligned16(w->conv_b))) return ROM_E_INVAL;
   }
-  if (B < 0 || L < 0 || !(eps >= 0.0f)) return ROM_E_INVAL;
+  if (B < 0 || L < 0) return ROM_E_INVAL;
   if (B == 0 || L == 0) return ROM_OK;
-  if (!x || !out || !ws || x == out) return ROM_E_INVAL;
-  if (!aligned16(x) || !aligned16(out) || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return ROM_E_INVAL;
-  if (B * L * d->top_k > (1ll << 30) || B > 65535) return ROM_E_UNSUPPORTED;
-  {
-    const float *states[] = {conv_in, ssm_in, conv_out, ssm_out};
-    for (const float *ptr : states)
-      if (ptr && !aligned16(ptr)) return ROM_E_INVAL;
-    if (L > kConvInPlaceMaxLen && ((conv_in && conv_in == conv_out) || (ssm_in && ssm_in == ssm_out))) return ROM_E_INVAL;
-  }
-  const int64_t N = B * L;
+  rc = check_variant_call(x, out, ws, B, L, d->top_k, eps, conv_in, ssm_in, conv_out, ssm_out);
+  if (rc != ROM_OK) return rc;
   const GdnPlan p = make_gdn_plan(d, B, L);
   if (ws_bytes < p.total) return ROM_E_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-
   char *base = static_cast<char *>(ws);
-  auto at = [&](size_t off) { return base + off; };
-  const int K = d->top_k, E = d->n_experts, H = d->n_heads, Dm = d->d_model;
-  const int Dk = H * d->d_k, Dv = H * d->d_v, Dp = 2 * Dv + 2 * Dk + 2 * H, Dc = 2 * Dk + Dv;
-  const bool multi = K > 1;
-  const int64_t S = N * K;
-  float *gate = reinterpret_cast<float *>(at(p.gate));
-  int32_t *offsets = reinterpret_cast<int32_t *>(at(p.offsets));
-  int32_t *inv_perm = reinterpret_cast<int32_t *>(at(p.inv_perm));
-  int32_t *tok_of_pos = reinterpret_cast<int32_t *>(at(p.tok_of_pos));
+  const int H = d->n_heads, Dk = H * d->d_k, Dv = H * d->d_v, Dp = 2 * Dv + 2 * Dk + 2 * H, Dc = 2 * Dk + Dv;
 
-  rom_dims rd;
-  memset(&rd, 0, sizeof(rd));
-  rd.d_model = Dm; rd.d_inner = Dv; rd.n_experts = E; rd.top_k = K; rd.n_experts_xdt = E;
-  rd.dtype = d->dtype; rd.gate_mode = d->gate_mode;
-  rom_weights rw;
-  memset(&rw, 0, sizeof(rw));
-  rw.w_router = w->w_router; rw.b_router = w->b_router;
-  StageMark mark;
-  rc = route_into(&rd, &rw, x, N, reinterpret_cast<int32_t *>(at(p.expert_idx)), gate,
-                  reinterpret_cast<int32_t *>(at(p.counts)), offsets, reinterpret_cast<int32_t *>(at(p.perm)), inv_perm,
-                  tok_of_pos, reinterpret_cast<int32_t *>(at(p.block_counts)), reinterpret_cast<float *>(at(p.logits)),
-                  nullptr, nullptr, s, &mark);
-  if (rc != ROM_OK) return rc;
-
-  // input projection z | q | k | v | b | a: one routed GEMM, rows back in token order
-  mark.begin(ROM_STAGE_IN_PROJ, s);
-  GemmArgs ga;
-  memset(&ga, 0, sizeof(ga));
-  ga.dtype = d->dtype;
-  ga.A = x; ga.lda = Dm; ga.a_rows = tok_of_pos; ga.a_span = N * Dm;
-  ga.W = w->w_in; ga.N = Dp; ga.K = Dm;
-  ga.n_groups = E; ga.M = S; ga.offsets = offsets;
-  ga.C = multi ? at(p.proj_sorted) : at(p.proj); ga.ldc = Dp; ga.c_rows = multi ? nullptr : tok_of_pos;
-  ROM_TRY(launch_grouped_gemm(ga, s));
-  if (multi)
-    ROM_TRY(launch_slot_sum(0, 0, at(p.proj_sorted), Dp, at(p.proj), Dp, inv_perm, N, K, Dp, nullptr, 0, nullptr, s));
-  mark.end(ROM_STAGE_IN_PROJ, s);
-
-  // short conv + SiLU over the channels q | k | v
-  mark.begin(ROM_STAGE_CONV, s);
-  {
-    float *ctmp = reinterpret_cast<float *>(at(p.conv_tmp));
-    const bool beside = conv_out && L > kConvInPlaceMaxLen;
-    ROM_TRY(launch_conv_silu(d->dtype, at(p.proj) + static_cast<size_t>(Dv) * 2, Dp, w->conv_w, w->conv_b, conv_in,
-                             beside ? ctmp : conv_out, at(p.qkv), B, L, Dc, s));
-    if (beside) {
-      const int64_t n = B * Dc * 3;
-      hipLaunchKernelGGL(copy_f32_kernel, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, s, ctmp, conv_out, n);
-      ROM_TRY(hipGetLastError());
-    }
-  }
-  mark.end(ROM_STAGE_CONV, s);
-
-  // delta rule, head norm, SiLU(z) gate
-  mark.begin(ROM_STAGE_SCAN, s);
-  ROM_TRY(launch_gdn_scan(at(p.qkv), Dc, 0, Dk, 2 * Dk, at(p.proj), Dp, Dv + Dc, Dv + Dc + H, w->dt_bias, w->A_log, w->norm_w,
-                          eps, B, L, H, d->d_k, ssm_in, ssm_out, reinterpret_cast<float *>(at(p.carry)), at(p.y), Dv, s));
-  mark.end(ROM_STAGE_SCAN, s);
-
-  // output projection and the gate-weighted combine
-  mark.begin(ROM_STAGE_OUT_PROJ, s);
-  memset(&ga, 0, sizeof(ga));
-  ga.dtype = d->dtype;
-  ga.A = at(p.y); ga.lda = Dv; ga.a_rows = tok_of_pos; ga.a_span = N * Dv;
-  ga.W = w->w_out; ga.N = Dm; ga.K = Dv;
-  ga.n_groups = E; ga.M = S; ga.offsets = offsets;
-  if (multi) {
-    ga.C = at(p.op_sorted); ga.ldc = Dm;
-    ROM_TRY(launch_grouped_gemm(ga, s));
-    mark.end(ROM_STAGE_OUT_PROJ, s);
-    mark.begin(ROM_STAGE_COMBINE, s);
-    ROM_TRY(launch_combine(d->dtype, at(p.op_sorted), inv_perm, gate, out, N, K, Dm, nullptr, s));
-    mark.end(ROM_STAGE_COMBINE, s);
-  } else {
-    ga.C = out; ga.ldc = Dm; ga.c_rows = tok_of_pos; ga.row_scale = gate;
-    ROM_TRY(launch_grouped_gemm(ga, s));
-    mark.end(ROM_STAGE_OUT_PROJ, s);
-  }
-  return ROM_OK;
+  VariantFrame f;
+  f.dtype = d->dtype; f.gate_mode = d->gate_mode; f.n_experts = d->n_experts; f.top_k = d->top_k; f.d_model = d->d_model;
+  f.d_proj = Dp; f.conv_col = Dv; f.d_conv_ch = Dc; f.d_y = Dv;          // z | q | k | v | b | a: the conv runs over q | k | v
+  f.w_router = w->w_router; f.b_router = w->b_router; f.w_in = w->w_in; f.conv_w = w->conv_w; f.conv_b = w->conv_b;
+  f.w_out = w->w_out;
+  f.expert_idx = p.expert_idx; f.gate = p.gate; f.counts = p.counts; f.offsets = p.offsets; f.perm = p.perm;
+  f.inv_perm = p.inv_perm; f.tok_of_pos = p.tok_of_pos; f.block_counts = p.block_counts; f.logits = p.logits;
+  f.proj = p.proj; f.proj_sorted = p.proj_sorted; f.conv_dst = p.qkv; f.y = p.y; f.op_sorted = p.op_sorted;
+  f.conv_tmp = p.conv_tmp;
+  return run_variant(f, x, B, L, conv_in, conv_out, out, base, s, [&](StageMark &mark) {
+    // delta rule, head norm, SiLU(z) gate
+    mark.begin(ROM_STAGE_SCAN, s);
+    ROM_TRY(launch_gdn_scan(base + p.qkv, Dc, 0, Dk, 2 * Dk, base + p.proj, Dp, Dv + Dc, Dv + Dc + H, w->dt_bias, w->A_log,
+                            w->norm_w, eps, B, L, H, d->d_k, ssm_in, ssm_out, reinterpret_cast<float *>(base + p.carry),
+                            base + p.y, Dv, s));
+    mark.end(ROM_STAGE_SCAN, s);
+    return static_cast<int>(ROM_OK);
+  });
 }
 
 int rom_gdn_step(const rom_gdn_dims *d, const rom_gdn_weights *w, const void *x, int64_t B, float eps, float *conv_state,
