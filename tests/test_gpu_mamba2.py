@@ -239,3 +239,20 @@ def test_mamba2_step_full_size():
         assert err <= TOL["bf16"]
     assert rel_err(to_np(ss), ss_ref.transpose(0, 1, 3, 2)) <= TOL["bf16"]
     assert rel_err(to_np(cs), cs_ref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_mamba2_random_shapes(seed):
+    """Shapes off the beaten path: odd lengths around chunk and segment borders, d_model not a multiple of 64,
+    odd expert counts, top-k up to E, both state sizes."""
+    rng = np.random.default_rng(900 + seed)
+    n_experts = int(rng.integers(1, 8))
+    cfg = get_mamba2_config(
+        "m2_small", cfg_id=70 + seed, batch=int(rng.integers(1, 4)), seq_len=int(rng.choice([1, 2, 63, 64, 65, 127, 257, 700, 1301])),
+        d_model=int(rng.choice([72, 136, 264])), d_inner=int(rng.choice([512, 1024])), d_state=int(rng.choice([64, 128])),
+        n_experts=n_experts, top_k=int(rng.integers(1, n_experts + 1)) if n_experts <= 4 else int(rng.integers(1, 4)),
+        gate_mode=int(rng.integers(0, 2)), weight_std=0.05)
+    print(f"[random {seed}] B={cfg.batch} L={cfg.seq_len} d_model={cfg.d_model} d_inner={cfg.d_inner} N={cfg.d_state} "
+          f"E={cfg.n_experts} K={cfg.top_k} gate_mode={cfg.gate_mode}", flush=True)
+    gpu, x_np, w_np = run_mamba2(cfg)
+    compare_mamba2(cfg, gpu, x_np, w_np)
