@@ -693,8 +693,10 @@ class RomStack:
 class RomFfnMoe:
     """An FFN-MoE layer (SwiGLU experts) that runs on the routing decision of a RomLayer call."""
 
-    def __init__(self, layer: RomLayer, d_ff: int, weights, eps: float = 1e-5):
-        self.layer, self.dims, self.d_ff, self.eps = layer, layer.dims, d_ff, eps
+    def __init__(self, layer, d_ff: int, weights, eps: float = 1e-5):
+        # layer: a RomLayer, or a RomMamba2Layer / RomGdnLayer (their routing_dims() carry what the FFN call reads)
+        dims = layer.dims if isinstance(layer.dims, RomDims) else layer.routing_dims()
+        self.layer, self.dims, self.d_ff, self.eps = layer, dims, d_ff, eps
         self.device = layer.device
         conv = lambda a, dt: (a if isinstance(a, torch.Tensor) else torch.from_numpy(a)).to(dt).to(self.device).contiguous()
         self.w_gate_up = conv(weights["w_gate_up"], layer.tdtype)
@@ -836,6 +838,13 @@ class RomMamba2Layer:
         d = self.dims
         return (B, d.d_inner + 2 * d.d_state, d.d_conv - 1), (B, d.d_inner // d.headdim, d.d_state, d.headdim)
 
+    def routing_dims(self) -> RomDims:
+        """What rom_ffn_moe_forward reads of a layer's dims (d_model, experts, top-k, dtype, gate mode), for an
+        FFN-MoE layer that runs on this layer's routing decision; the Mamba-only fields hold valid placeholders."""
+        d = self.dims
+        return RomDims(d.d_model, 2 * d.d_model, 16, 4, max(d.d_model // 16, 1), d.n_experts, d.top_k, d.n_experts, d.dtype,
+                       d.gate_mode)
+
     def forward(self, x: torch.Tensor, conv_state=None, ssm_state=None, return_states=False):
         B, L = int(x.shape[0]), int(x.shape[1])
         out = torch.empty_like(x)
@@ -896,6 +905,12 @@ class RomGdnLayer:
     def state_shapes(self, B: int):
         d = self.dims
         return (B, 2 * d.n_heads * d.d_k + d.n_heads * d.d_v, d.d_conv - 1), (B, d.n_heads, d.d_k, d.d_v)
+
+    def routing_dims(self) -> RomDims:
+        """What rom_ffn_moe_forward reads of a layer's dims, for an FFN-MoE layer on this layer's routing decision."""
+        d = self.dims
+        return RomDims(d.d_model, 2 * d.d_model, 16, 4, max(d.d_model // 16, 1), d.n_experts, d.top_k, d.n_experts, d.dtype,
+                       d.gate_mode)
 
     def ws_view(self, name: str, B: int, L: int) -> torch.Tensor:
         """Intermediate tensor `name` of the last forward call with these B, L."""

@@ -256,3 +256,41 @@ def test_mamba2_random_shapes(seed):
           f"E={cfg.n_experts} K={cfg.top_k} gate_mode={cfg.gate_mode}", flush=True)
     gpu, x_np, w_np = run_mamba2(cfg)
     compare_mamba2(cfg, gpu, x_np, w_np)
+
+
+@pytest.mark.parametrize("variant", ["mamba2", "gdn"])
+def test_ffn_moe_runs_on_a_variant_layers_routing(variant):
+    """The hybrid pair of the appendix (Eq. (14), (15)) with a variant as the RoM layer: the FFN-MoE layer reads
+    the variant layer's output and runs on ITS routing decision (offsets, permutation, gates from its workspace)."""
+    from oracle import rom_oracle as O
+    from oracle import rom_gdn_oracle as G
+    from paper_2506_18145_amd import RomFfnMoe, RomGdnLayer
+    from rom_synth import get_gdn_config, make_ffn_weights, make_gdn_input, make_gdn_weights
+    if variant == "mamba2":
+        cfg = get_mamba2_config("m2_mid", batch=2, seq_len=333, cfg_id=90, weight_std=0.08)
+        w_np, x_np = make_mamba2_weights(cfg), make_mamba2_input(cfg)
+        layer = RomMamba2Layer(cfg, w_np, eps=EPS)
+    else:
+        cfg = get_gdn_config("gdn_mid", batch=2, seq_len=333, cfg_id=91, weight_std=0.08)
+        w_np, x_np = make_gdn_weights(cfg), make_gdn_input(cfg)
+        layer = RomGdnLayer(cfg, w_np, eps=EPS)
+    B, L, N = cfg.batch, cfg.seq_len, cfg.batch * cfg.seq_len
+    mid = layer.forward(layer.to_device(x_np))
+    torch.cuda.synchronize()
+    idx = to_np(layer.ws_view("expert_idx", B, L))
+    if variant == "mamba2":
+        ref = M.rom_mamba2_forward(x_np, w_np, cfg.top_k, cfg.gate_mode, cfg.headdim, EPS, expert_idx=idx)
+    else:
+        ref = G.rom_gdn_forward(x_np, w_np, cfg.top_k, cfg.gate_mode, cfg.n_heads, cfg.d_k, EPS, expert_idx=idx)
+    assert rel_err(to_np(mid), ref["out"]) <= TOL["bf16"]
+    fw = make_ffn_weights(cfg, 768)
+    ffn = RomFfnMoe(layer, 768, fw, eps=EPS)
+    routing = {k: layer.ws_view(k, B, L) for k in ("offsets", "perm", "inv_perm", "gate")}
+    out = ffn.forward(mid, routing, pre_norm=True, add_skip=True)
+    torch.cuda.synchronize()
+    # the FFN on the layer's own (device) output, so that the layer's rounding is not counted twice
+    mid_np = to_np(mid).reshape(N, -1).astype(np.float64)
+    want = O.ffn_moe_forward(mid_np, fw["w_gate_up"], fw["w_down"], ref["expert_idx"], ref["gate"], fw["norm_w"], EPS,
+                             skip=True)
+    assert rel_err(to_np(out).reshape(N, -1), want) <= TOL["bf16"]
+    assert np.max(np.abs(want - mid_np)) > 0.05 * np.max(np.abs(want))      # the FFN branch is visible
