@@ -260,6 +260,12 @@ ROM_API int rom_layer_backward_saved(const rom_dims *dims, const rom_weights *w,
 ROM_API int rom_fold_norm(const rom_dims *dims, const void *w_in, const float *norm_weight,
                   void *w_in_folded, void *hip_stream);
 
+/* The same for any projection weight stored [n_rows][d_model] (the input projections of the Mamba2
+ * and Gated DeltaNet layers below): w_folded[r, d] = w[r, d] * norm_weight[d], rounded once to the
+ * type.  w, w_folded T [n_rows, d_model] (device; may be the same buffer); dtype ROM_DTYPE_*. */
+ROM_API int rom_fold_norm_rows(int dtype, const void *w, const float *norm_weight, void *w_folded,
+                               int64_t n_rows, int32_t d_model, void *hip_stream);
+
 /* One block: arguments as rom_layer_forward plus
  *   norm_weight  f32 [d_model] (device, 16-byte aligned), eps >= 0
  * out must not alias x (x is read again for the skip).  Workspace: rom_workspace_bytes(dims, B, L).
@@ -447,6 +453,19 @@ ROM_API int rom_mamba2_forward(const rom_mamba2_dims *dims, const rom_mamba2_wei
                                const float *ssm_state_in, void *out, float *conv_state_out,
                                float *ssm_state_out, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* The pre-norm residual block around the layer above (appendix: every layer sits behind a pre-norm
+ * and a skip connection): out = x + layer(RMSNorm(x)), RMSNorm with scale norm_weight (f32 [d_model],
+ * device) and norm_eps.  As in rom_block_forward the norm is never materialised: the router applies it
+ * itself, the input projection runs on the raw x with w->w_in FOLDED (rom_fold_norm_rows over its
+ * E * (2*d_inner + 2*d_state + n_heads) rows) and scales its rows by 1/rms, the skip is added where the
+ * output projection or the combine writes out.  out must not alias x (ROM_E_INVAL).  Everything else
+ * as rom_mamba2_forward. */
+ROM_API int rom_mamba2_block_forward(const rom_mamba2_dims *dims, const rom_mamba2_weights *w,
+                                     const float *norm_weight, float norm_eps, const void *x, int64_t B,
+                                     int64_t L, float eps, const float *conv_state_in,
+                                     const float *ssm_state_in, void *out, float *conv_state_out,
+                                     float *ssm_state_out, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* One new token for each of B sequences (the recurrent form of the layer above): x, out T [B, d_model];
  * conv_state and ssm_state (layouts above, both required) are read and updated in place.
  *   ws   rom_mamba2_workspace_bytes(dims, B, 1)
@@ -533,6 +552,14 @@ ROM_API int rom_gdn_forward(const rom_gdn_dims *dims, const rom_gdn_weights *w, 
                             int64_t L, float eps, const float *conv_state_in, const float *ssm_state_in,
                             void *out, float *conv_state_out, float *ssm_state_out, void *ws,
                             size_t ws_bytes, void *hip_stream);
+
+/* The pre-norm residual block around it: out = x + layer(RMSNorm(x)); w->w_in FOLDED with norm_weight
+ * (rom_fold_norm_rows over its E * (2*D_v + 2*D_k + 2*H) rows); see rom_mamba2_block_forward. */
+ROM_API int rom_gdn_block_forward(const rom_gdn_dims *dims, const rom_gdn_weights *w, const float *norm_weight,
+                                  float norm_eps, const void *x, int64_t B, int64_t L, float eps,
+                                  const float *conv_state_in, const float *ssm_state_in, void *out,
+                                  float *conv_state_out, float *ssm_state_out, void *ws, size_t ws_bytes,
+                                  void *hip_stream);
 
 /* One new token for each of B sequences (the recurrent form of rom_gdn_forward): x, out T [B, d_model];
  * conv_state and ssm_state (layouts above, both required) are read and updated in place.

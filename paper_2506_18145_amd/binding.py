@@ -151,6 +151,14 @@ def load_library() -> ctypes.CDLL:
     lib.rom_mamba2_forward.restype = ctypes.c_int
     lib.rom_mamba2_forward.argtypes = [ctypes.POINTER(RomMamba2Dims), ctypes.POINTER(_RomMamba2Weights), P, I64, I64,
                                        F32, P, P, P, P, P, P, SZ, P]
+    lib.rom_mamba2_block_forward.restype = ctypes.c_int
+    lib.rom_mamba2_block_forward.argtypes = [ctypes.POINTER(RomMamba2Dims), ctypes.POINTER(_RomMamba2Weights), P, F32, P,
+                                             I64, I64, F32, P, P, P, P, P, P, SZ, P]
+    lib.rom_gdn_block_forward.restype = ctypes.c_int
+    lib.rom_gdn_block_forward.argtypes = [ctypes.POINTER(RomGdnDims), ctypes.POINTER(_RomGdnWeights), P, F32, P, I64, I64,
+                                          F32, P, P, P, P, P, P, SZ, P]
+    lib.rom_fold_norm_rows.restype = ctypes.c_int
+    lib.rom_fold_norm_rows.argtypes = [ctypes.c_int, P, P, P, I64, ctypes.c_int32, P]
     lib.rom_mamba2_step.restype = ctypes.c_int
     lib.rom_mamba2_step.argtypes = [ctypes.POINTER(RomMamba2Dims), ctypes.POINTER(_RomMamba2Weights), P, I64, F32, P, P,
                                     P, P, SZ, P]
@@ -385,6 +393,20 @@ def rom_mamba2_forward(dims, weights, x, B, L, eps, conv_state_in, ssm_state_in,
     _check(code, "rom_mamba2_forward")
 
 
+def rom_fold_norm_rows(dtype, w, norm_weight, w_folded, n_rows, d_model):
+    _check(load_library().rom_fold_norm_rows(dtype, _ptr(w), _ptr(norm_weight), _ptr(w_folded), n_rows, d_model, _stream()),
+           "rom_fold_norm_rows")
+
+
+def rom_mamba2_block_forward(dims, weights, norm_weight, norm_eps, x, B, L, eps, conv_state_in, ssm_state_in, out,
+                             conv_state_out, ssm_state_out, ws):
+    code = load_library().rom_mamba2_block_forward(
+        ctypes.byref(dims), ctypes.byref(_mamba2_weights_struct(weights)), _ptr(norm_weight), norm_eps, _ptr(x), B, L, eps,
+        _ptr(conv_state_in), _ptr(ssm_state_in), _ptr(out), _ptr(conv_state_out), _ptr(ssm_state_out), _ptr(ws),
+        ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check(code, "rom_mamba2_block_forward")
+
+
 def rom_mamba2_step(dims, weights, x, B, eps, conv_state, ssm_state, out, ws):
     code = load_library().rom_mamba2_step(
         ctypes.byref(dims), ctypes.byref(_mamba2_weights_struct(weights)), _ptr(x), B, eps, _ptr(conv_state),
@@ -414,6 +436,15 @@ def rom_gdn_step(dims, weights, x, B, eps, conv_state, ssm_state, out, ws):
         ctypes.byref(dims), ctypes.byref(_gdn_weights_struct(weights)), _ptr(x), B, eps, _ptr(conv_state), _ptr(ssm_state),
         _ptr(out), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream())
     _check(code, "rom_gdn_step")
+
+
+def rom_gdn_block_forward(dims, weights, norm_weight, norm_eps, x, B, L, eps, conv_state_in, ssm_state_in, out,
+                          conv_state_out, ssm_state_out, ws):
+    code = load_library().rom_gdn_block_forward(
+        ctypes.byref(dims), ctypes.byref(_gdn_weights_struct(weights)), _ptr(norm_weight), norm_eps, _ptr(x), B, L, eps,
+        _ptr(conv_state_in), _ptr(ssm_state_in), _ptr(out), _ptr(conv_state_out), _ptr(ssm_state_out), _ptr(ws),
+        ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check(code, "rom_gdn_block_forward")
 
 
 def rom_gdn_forward(dims, weights, x, B, L, eps, conv_state_in, ssm_state_in, out, conv_state_out, ssm_state_out, ws):
@@ -857,6 +888,32 @@ class RomMamba2Layer:
                            self.workspace(max(B, 1), max(L, 1)))
         return (out, conv_out, ssm_out) if return_states else out
 
+    def block_weights(self, pre_norm_w: torch.Tensor) -> Dict[str, Optional[torch.Tensor]]:
+        """The weight set the block entry point expects: w_in with the pre-norm's scale folded into its
+        columns (rom_fold_norm_rows, cached per pre-norm tensor), everything else shared."""
+        key = (pre_norm_w.data_ptr(), pre_norm_w._version)
+        if getattr(self, "_fold_key", None) != key:
+            w_in = self.weights["w_in"]
+            folded = torch.empty_like(w_in)
+            rom_fold_norm_rows(self.dims.dtype, w_in, pre_norm_w, folded, w_in.shape[0] * w_in.shape[1], w_in.shape[2])
+            self._folded = dict(self.weights, w_in=folded)
+            self._fold_key = key
+        return self._folded
+
+    def block_forward(self, x: torch.Tensor, pre_norm_w: torch.Tensor, pre_norm_eps: float = 1e-5, conv_state=None,
+                      ssm_state=None, return_states=False):
+        """out = x + layer(RMSNorm(x)); pre_norm_w f32 [d_model] on the device."""
+        B, L = int(x.shape[0]), int(x.shape[1])
+        out = torch.empty_like(x)
+        conv_out = ssm_out = None
+        if return_states:
+            cs, ss = self.state_shapes(B)
+            conv_out = torch.empty(cs, dtype=torch.float32, device=self.device)
+            ssm_out = torch.empty(ss, dtype=torch.float32, device=self.device)
+        rom_mamba2_block_forward(self.dims, self.block_weights(pre_norm_w), pre_norm_w, pre_norm_eps, x, B, L, self.eps,
+                                 conv_state, ssm_state, out, conv_out, ssm_out, self.workspace(max(B, 1), max(L, 1)))
+        return (out, conv_out, ssm_out) if return_states else out
+
     def step(self, x: torch.Tensor, conv_state: torch.Tensor, ssm_state: torch.Tensor, out=None) -> torch.Tensor:
         """x [B, d_model]; the states are updated in place."""
         B = int(x.shape[0])
@@ -943,6 +1000,32 @@ class RomGdnLayer:
             ssm_out = torch.empty(ss, dtype=torch.float32, device=self.device)
         rom_gdn_forward(self.dims, self.weights, x, B, L, self.eps, conv_state, ssm_state, out, conv_out, ssm_out,
                         self.workspace(max(B, 1), max(L, 1)))
+        return (out, conv_out, ssm_out) if return_states else out
+
+    def block_weights(self, pre_norm_w: torch.Tensor) -> Dict[str, Optional[torch.Tensor]]:
+        """The weight set the block entry point expects: w_in with the pre-norm's scale folded into its
+        columns (rom_fold_norm_rows, cached per pre-norm tensor), everything else shared."""
+        key = (pre_norm_w.data_ptr(), pre_norm_w._version)
+        if getattr(self, "_fold_key", None) != key:
+            w_in = self.weights["w_in"]
+            folded = torch.empty_like(w_in)
+            rom_fold_norm_rows(self.dims.dtype, w_in, pre_norm_w, folded, w_in.shape[0] * w_in.shape[1], w_in.shape[2])
+            self._folded = dict(self.weights, w_in=folded)
+            self._fold_key = key
+        return self._folded
+
+    def block_forward(self, x: torch.Tensor, pre_norm_w: torch.Tensor, pre_norm_eps: float = 1e-5, conv_state=None,
+                      ssm_state=None, return_states=False):
+        """out = x + layer(RMSNorm(x)); pre_norm_w f32 [d_model] on the device."""
+        B, L = int(x.shape[0]), int(x.shape[1])
+        out = torch.empty_like(x)
+        conv_out = ssm_out = None
+        if return_states:
+            cs, ss = self.state_shapes(B)
+            conv_out = torch.empty(cs, dtype=torch.float32, device=self.device)
+            ssm_out = torch.empty(ss, dtype=torch.float32, device=self.device)
+        rom_gdn_block_forward(self.dims, self.block_weights(pre_norm_w), pre_norm_w, pre_norm_eps, x, B, L, self.eps,
+                              conv_state, ssm_state, out, conv_out, ssm_out, self.workspace(max(B, 1), max(L, 1)))
         return (out, conv_out, ssm_out) if return_states else out
 
     def step(self, x: torch.Tensor, conv_state: torch.Tensor, ssm_state: torch.Tensor, out=None) -> torch.Tensor:

@@ -541,6 +541,10 @@ struct VariantFrame {
   // byte offsets inside the workspace
   size_t expert_idx, gate, counts, offsets, perm, inv_perm, tok_of_pos, block_counts, logits;
   size_t proj, proj_sorted, conv_dst, y, op_sorted, conv_tmp;
+  // pre-norm residual block (out = x + layer(RMSNorm(x))): the norm's scale (w_in is then the folded weight) or NULL
+  const float *pre_norm_w;
+  float pre_norm_eps;
+  size_t rstd;                 // f32 [N]
 };
 
 // argument checks both variants share (after their own dims / weights checks)
@@ -581,10 +585,15 @@ int run_variant(const VariantFrame &f, const void *x, int64_t B, int64_t L, cons
   memset(&rw, 0, sizeof(rw));
   rw.w_router = f.w_router; rw.b_router = f.b_router;
   StageMark mark;
+  BlockOpts blk;
+  blk.norm_w = f.pre_norm_w;
+  blk.eps = f.pre_norm_eps;
+  const bool block = f.pre_norm_w != nullptr;
+  float *rstd = block ? reinterpret_cast<float *>(at(f.rstd)) : nullptr;
   int rc = route_into(&rd, &rw, x, N, reinterpret_cast<int32_t *>(at(f.expert_idx)), gate,
                       reinterpret_cast<int32_t *>(at(f.counts)), offsets, reinterpret_cast<int32_t *>(at(f.perm)), inv_perm,
                       tok_of_pos, reinterpret_cast<int32_t *>(at(f.block_counts)), reinterpret_cast<float *>(at(f.logits)),
-                      nullptr, nullptr, s, &mark);
+                      block ? &blk : nullptr, rstd, s, &mark);
   if (rc != ROM_OK) return rc;
 
   // input projection: one routed GEMM, rows back in token order (K > 1: per-slot rows, then their sum)
@@ -596,10 +605,12 @@ int run_variant(const VariantFrame &f, const void *x, int64_t B, int64_t L, cons
   ga.W = f.w_in; ga.N = f.d_proj; ga.K = f.d_model;
   ga.n_groups = f.n_experts; ga.M = S; ga.offsets = offsets;
   ga.C = multi ? at(f.proj_sorted) : at(f.proj); ga.ldc = f.d_proj; ga.c_rows = multi ? nullptr : tok_of_pos;
+  // pre-norm block: x @ (W . norm_w)^T scaled by the token's 1/rms is RMSNorm(x) @ W^T
+  if (!multi) ga.row_scale = rstd;
   ROM_TRY(launch_grouped_gemm(ga, s));
   if (multi)
     ROM_TRY(launch_slot_sum(0, 0, at(f.proj_sorted), f.d_proj, at(f.proj), f.d_proj, inv_perm, N, f.top_k, f.d_proj, nullptr, 0,
-                            nullptr, s));
+                            rstd, s));
   mark.end(ROM_STAGE_IN_PROJ, s);
 
   // short conv + SiLU, read in place from the projection's output
@@ -632,10 +643,11 @@ int run_variant(const VariantFrame &f, const void *x, int64_t B, int64_t L, cons
     ROM_TRY(launch_grouped_gemm(ga, s));
     mark.end(ROM_STAGE_OUT_PROJ, s);
     mark.begin(ROM_STAGE_COMBINE, s);
-    ROM_TRY(launch_combine(f.dtype, at(f.op_sorted), inv_perm, gate, out, N, f.top_k, f.d_model, nullptr, s));
+    ROM_TRY(launch_combine(f.dtype, at(f.op_sorted), inv_perm, gate, out, N, f.top_k, f.d_model, block ? x : nullptr, s));
     mark.end(ROM_STAGE_COMBINE, s);
   } else {
     ga.C = out; ga.ldc = f.d_model; ga.c_rows = tok_of_pos; ga.row_scale = gate;
+    if (block) ga.residual = x;                                             // skip connection
     ROM_TRY(launch_grouped_gemm(ga, s));
     mark.end(ROM_STAGE_OUT_PROJ, s);
   }
@@ -745,6 +757,23 @@ int rom_fold_norm(const rom_dims *dims, const void *w_in, const float *norm_weig
   else
     hipLaunchKernelGGL(fold_cols_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(w_in),
                        norm_weight, static_cast<float *>(w_in_folded), rows, dims->d_model);
+  return hipGetLastError() == hipSuccess ? ROM_OK : ROM_E_HIP;
+}
+
+int rom_fold_norm_rows(int dtype, const void *w, const float *norm_weight, void *w_folded, int64_t n_rows, int32_t d_model,
+                       void *hip_stream) {
+  if (dtype != ROM_DTYPE_F32 && dtype != ROM_DTYPE_BF16) return ROM_E_INVAL;
+  if (!w || !norm_weight || !w_folded || n_rows < 0 || d_model <= 0) return ROM_E_INVAL;
+  if (n_rows == 0) return ROM_OK;
+  const int64_t n = n_rows * d_model;
+  const dim3 grid(static_cast<unsigned>(ceil_div(n, 256)));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL(fold_cols_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(w), norm_weight,
+                       static_cast<bf16_t *>(w_folded), n_rows, d_model);
+  else
+    hipLaunchKernelGGL(fold_cols_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(w), norm_weight,
+                       static_cast<float *>(w_folded), n_rows, d_model);
   return hipGetLastError() == hipSuccess ? ROM_OK : ROM_E_HIP;
 }
 
@@ -975,7 +1004,7 @@ namespace {
 struct Mamba2Plan {           // byte offsets inside the workspace
   size_t total;
   size_t expert_idx, gate, counts, offsets, perm, inv_perm, tok_of_pos, block_counts, logits;
-  size_t zxbcdt, zx_sorted, xbc, yz, g, op_sorted, carry, conv_tmp;
+  size_t zxbcdt, zx_sorted, xbc, yz, g, op_sorted, carry, conv_tmp, rstd;
 };
 
 int check_mamba2_dims(const rom_mamba2_dims *d) {
@@ -1020,6 +1049,7 @@ Mamba2Plan make_mamba2_plan(const rom_mamba2_dims *d, int64_t n_seq, int64_t seq
   p.carry = take(ssd_carry_bytes(n_seq, seq_len, static_cast<int>(H), d->d_state));
   // the conv writes its end state beside the old one when a sequence is cut into runs
   p.conv_tmp = take(seq_len > kConvInPlaceMaxLen ? static_cast<size_t>(n_seq) * Dc * 3 * 4 : 0);
+  p.rstd = take(N * 4);
   p.total = off;
   return p;
 }
@@ -1050,9 +1080,31 @@ int rom_mamba2_workspace_layout(const rom_mamba2_dims *dims, int64_t B, int64_t 
   return ROM_OK;
 }
 
+namespace {
+int mamba2_impl(const rom_mamba2_dims *d, const rom_mamba2_weights *w, const float *pre_norm_w, float pre_norm_eps,
+                const void *x, int64_t B, int64_t L, float eps, const float *conv_in, const float *ssm_in, void *out,
+                float *conv_out, float *ssm_out, void *ws, size_t ws_bytes, void *hip_stream);
+}
+
 int rom_mamba2_forward(const rom_mamba2_dims *d, const rom_mamba2_weights *w, const void *x, int64_t B, int64_t L,
                        float eps, const float *conv_in, const float *ssm_in, void *out, float *conv_out, float *ssm_out,
                        void *ws, size_t ws_bytes, void *hip_stream) {
+  return mamba2_impl(d, w, nullptr, 0.0f, x, B, L, eps, conv_in, ssm_in, out, conv_out, ssm_out, ws, ws_bytes, hip_stream);
+}
+
+int rom_mamba2_block_forward(const rom_mamba2_dims *d, const rom_mamba2_weights *w, const float *norm_weight,
+                             float norm_eps, const void *x, int64_t B, int64_t L, float eps, const float *conv_in,
+                             const float *ssm_in, void *out, float *conv_out, float *ssm_out, void *ws, size_t ws_bytes,
+                             void *hip_stream) {
+  if (!norm_weight || !aligned16(norm_weight) || !(norm_eps >= 0.0f) || out == x) return ROM_E_INVAL;
+  return mamba2_impl(d, w, norm_weight, norm_eps, x, B, L, eps, conv_in, ssm_in, out, conv_out, ssm_out, ws, ws_bytes,
+                     hip_stream);
+}
+
+namespace {
+int mamba2_impl(const rom_mamba2_dims *d, const rom_mamba2_weights *w, const float *pre_norm_w, float pre_norm_eps,
+                const void *x, int64_t B, int64_t L, float eps, const float *conv_in, const float *ssm_in, void *out,
+                float *conv_out, float *ssm_out, void *ws, size_t ws_bytes, void *hip_stream) {
   int rc = check_mamba2_dims(d);
   if (rc != ROM_OK) return rc;
   if (!w) return ROM_E_INVAL;
@@ -1081,6 +1133,7 @@ int rom_mamba2_forward(const rom_mamba2_dims *d, const rom_mamba2_weights *w, co
   f.inv_perm = p.inv_perm; f.tok_of_pos = p.tok_of_pos; f.block_counts = p.block_counts; f.logits = p.logits;
   f.proj = p.zxbcdt; f.proj_sorted = p.zx_sorted; f.conv_dst = p.xbc; f.y = p.g; f.op_sorted = p.op_sorted;
   f.conv_tmp = p.conv_tmp;
+  f.pre_norm_w = pre_norm_w; f.pre_norm_eps = pre_norm_eps; f.rstd = p.rstd;
   return run_variant(f, x, B, L, conv_in, conv_out, out, base, s, [&](StageMark &mark) {
     // recurrence, D skip, SiLU(z) gate
     mark.begin(ROM_STAGE_SCAN, s);
@@ -1095,6 +1148,7 @@ int rom_mamba2_forward(const rom_mamba2_dims *d, const rom_mamba2_weights *w, co
     return static_cast<int>(ROM_OK);
   });
 }
+}  // namespace
 
 int rom_mamba2_step(const rom_mamba2_dims *d, const rom_mamba2_weights *w, const void *x, int64_t B, float eps,
                     float *conv_state, float *ssm_state, void *out, void *ws, size_t ws_bytes, void *hip_stream) {
@@ -1108,7 +1162,7 @@ namespace {
 struct GdnPlan {              // byte offsets inside the workspace
   size_t total;
   size_t expert_idx, gate, counts, offsets, perm, inv_perm, tok_of_pos, block_counts, logits;
-  size_t proj, proj_sorted, qkv, y, op_sorted, conv_tmp, carry;
+  size_t proj, proj_sorted, qkv, y, op_sorted, conv_tmp, carry, rstd;
 };
 
 int check_gdn_dims(const rom_gdn_dims *d) {
@@ -1150,6 +1204,7 @@ GdnPlan make_gdn_plan(const rom_gdn_dims *d, int64_t n_seq, int64_t seq_len) {
   p.op_sorted = K > 1 ? take(S * Dm * 2) : kNone;
   p.conv_tmp = take(seq_len > kConvInPlaceMaxLen ? static_cast<size_t>(n_seq) * Dc * 3 * 4 : 0);
   p.carry = take(gdn_carry_bytes(n_seq, seq_len, d->n_heads, d->d_k));
+  p.rstd = take(N * 4);
   p.total = off;
   return p;
 }
@@ -1179,9 +1234,30 @@ int rom_gdn_workspace_layout(const rom_gdn_dims *dims, int64_t B, int64_t L, rom
   return ROM_OK;
 }
 
+namespace {
+int gdn_impl(const rom_gdn_dims *d, const rom_gdn_weights *w, const float *pre_norm_w, float pre_norm_eps, const void *x,
+             int64_t B, int64_t L, float eps, const float *conv_in, const float *ssm_in, void *out, float *conv_out,
+             float *ssm_out, void *ws, size_t ws_bytes, void *hip_stream);
+}
+
 int rom_gdn_forward(const rom_gdn_dims *d, const rom_gdn_weights *w, const void *x, int64_t B, int64_t L, float eps,
                     const float *conv_in, const float *ssm_in, void *out, float *conv_out, float *ssm_out, void *ws,
                     size_t ws_bytes, void *hip_stream) {
+  return gdn_impl(d, w, nullptr, 0.0f, x, B, L, eps, conv_in, ssm_in, out, conv_out, ssm_out, ws, ws_bytes, hip_stream);
+}
+
+int rom_gdn_block_forward(const rom_gdn_dims *d, const rom_gdn_weights *w, const float *norm_weight, float norm_eps,
+                          const void *x, int64_t B, int64_t L, float eps, const float *conv_in, const float *ssm_in,
+                          void *out, float *conv_out, float *ssm_out, void *ws, size_t ws_bytes, void *hip_stream) {
+  if (!norm_weight || !aligned16(norm_weight) || !(norm_eps >= 0.0f) || out == x) return ROM_E_INVAL;
+  return gdn_impl(d, w, norm_weight, norm_eps, x, B, L, eps, conv_in, ssm_in, out, conv_out, ssm_out, ws, ws_bytes,
+                  hip_stream);
+}
+
+namespace {
+int gdn_impl(const rom_gdn_dims *d, const rom_gdn_weights *w, const float *pre_norm_w, float pre_norm_eps, const void *x,
+             int64_t B, int64_t L, float eps, const float *conv_in, const float *ssm_in, void *out, float *conv_out,
+             float *ssm_out, void *ws, size_t ws_bytes, void *hip_stream) {
   int rc = check_gdn_dims(d);
   if (rc != ROM_OK) return rc;
   if (!w) return ROM_E_INVAL;
@@ -1210,6 +1286,7 @@ int rom_gdn_forward(const rom_gdn_dims *d, const rom_gdn_weights *w, const void 
   f.inv_perm = p.inv_perm; f.tok_of_pos = p.tok_of_pos; f.block_counts = p.block_counts; f.logits = p.logits;
   f.proj = p.proj; f.proj_sorted = p.proj_sorted; f.conv_dst = p.qkv; f.y = p.y; f.op_sorted = p.op_sorted;
   f.conv_tmp = p.conv_tmp;
+  f.pre_norm_w = pre_norm_w; f.pre_norm_eps = pre_norm_eps; f.rstd = p.rstd;
   return run_variant(f, x, B, L, conv_in, conv_out, out, base, s, [&](StageMark &mark) {
     // delta rule, head norm, SiLU(z) gate
     mark.begin(ROM_STAGE_SCAN, s);
@@ -1220,6 +1297,7 @@ int rom_gdn_forward(const rom_gdn_dims *d, const rom_gdn_weights *w, const void 
     return static_cast<int>(ROM_OK);
   });
 }
+}  // namespace
 
 int rom_gdn_step(const rom_gdn_dims *d, const rom_gdn_weights *w, const void *x, int64_t B, float eps, float *conv_state,
                  float *ssm_state, void *out, void *ws, size_t ws_bytes, void *hip_stream) {

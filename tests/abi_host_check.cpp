@@ -180,6 +180,18 @@ int main() {
     CHECK(rom_mamba2_forward(&m, &mw, addr, 0, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_OK);
     CHECK(rom_mamba2_forward(&m, &mw, addr, 1, 64, 1e-5f, nullptr, nullptr, addr, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);          // out == x
     CHECK(rom_mamba2_forward(nullptr, &mw, addr, 1, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+    {   // the pre-norm block: the layer's checks plus its own
+      const float *nw = reinterpret_cast<const float *>(addr);
+      CHECK(rom_mamba2_block_forward(&m, &mw, nullptr, 1e-5f, addr, 1, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+      CHECK(rom_mamba2_block_forward(&m, &mw, nw, -1.0f, addr, 1, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+      CHECK(rom_mamba2_block_forward(&m, &mw, nw, 1e-5f, addr, 1, 64, 1e-5f, nullptr, nullptr, addr, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+      CHECK(rom_mamba2_block_forward(&m, &mw, nw, 1e-5f, addr, 1, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+      CHECK(rom_mamba2_block_forward(&m, &mw, nw, 1e-5f, addr, 0, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_OK);
+      CHECK(rom_fold_norm_rows(7, addr, nw, addr, 4, 64, nullptr) == ROM_E_INVAL);
+      CHECK(rom_fold_norm_rows(ROM_DTYPE_BF16, nullptr, nw, addr, 4, 64, nullptr) == ROM_E_INVAL);
+      CHECK(rom_fold_norm_rows(ROM_DTYPE_BF16, addr, nw, addr, -1, 64, nullptr) == ROM_E_INVAL);
+      CHECK(rom_fold_norm_rows(ROM_DTYPE_BF16, addr, nw, addr, 0, 64, nullptr) == ROM_OK);
+    }
   }
 
   // ---- RoM on Gated DeltaNet: planning and validation
@@ -217,6 +229,10 @@ int main() {
     CHECK(rom_gdn_step(&m, &gw, addr, 4, 1e-5f, nullptr, st, addr + 4096, addr, 4096, nullptr) == ROM_E_INVAL);
     CHECK(rom_gdn_step(&m, &gw, addr, 4, 1e-5f, st, st, addr + 4096, addr, 4096, nullptr) == ROM_E_WORKSPACE);
     CHECK(rom_gdn_step(&m, &gw, addr, 0, 1e-5f, nullptr, nullptr, addr + 4096, addr, 4096, nullptr) == ROM_OK);
+    CHECK(rom_gdn_block_forward(&m, &gw, nullptr, 1e-5f, addr, 1, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_gdn_block_forward(&m, &gw, st, 1e-5f, addr, 1, 64, 1e-5f, nullptr, nullptr, addr, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_gdn_block_forward(&m, &gw, st, 1e-5f, addr, 1, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+    CHECK(rom_gdn_block_forward(&m, &gw, st, 1e-5f, addr, 0, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_OK);
   }
 
   // ---- strings and the profiling bookkeeping
