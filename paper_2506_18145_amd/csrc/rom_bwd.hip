@@ -1035,6 +1035,216 @@ __global__ __launch_bounds__(512) void wgrad_bf16_big_kernel(const bf16_t *__res
   }
 }
 
+// The 256 x 256 contraction once more, for outputs that are whole multiples of the tile: the operand
+// rows go from global memory straight into LDS exactly as they lie in memory - position-major, 256
+// columns = 512 bytes per position (global_load_lds_dwordx4: lane l of a wave deposits its 16 bytes
+// at M0 + 16 l) - and the MFMA fragments, which want eight consecutive POSITIONS of one column per
+// lane, are read with the transposing LDS read (ds_read_b64_tr_b16: the 16 lanes of a group name four
+// rows of 16 columns, lane i receives column i of the four rows).  No register transposes, no LDS
+// writes and no load -> park dependency are left in the loop.  A slab is 64 positions; LDS is a
+// ring of five half-slab slots of 32 KiB (A rows of slab m, B rows of slab m, A rows of slab m + 1, ...)
+// filled in ring order, four DMA instructions per wave and half slab, so that "vmcnt(4)" means
+// "everything but the newest half slab I asked for has landed".  The 16-byte chunk c of row r lies
+// at position c ^ 4 (r & 3) of its row (the swizzle is applied where the global address is formed):
+// the four rows x 64 bytes that 32 lanes read at a time then cover all 64 banks once.
+// Row indices (positions -> rows of the operand) are uniform per wave and instruction half: they
+// are read through the scalar cache one slab before the DMA that uses them is issued.
+// Positions past the group's end are fetched from whatever valid row follows and zeroed in LDS
+// before the last slab is multiplied.
+constexpr bool kUseWgradDma = true;
+constexpr int kWdSlots = 5;
+constexpr int kWdSlotBytes = kWgSlab * kWgBig * 2;         // 64 positions x 256 columns x 2 bytes
+constexpr int kWdSmem = kWdSlots * kWdSlotBytes;           // 160 KiB
+constexpr int kWdInstr = 4;                                // DMA instructions per wave and half slab (2 rows each)
+typedef short i16x4_t __attribute__((ext_vector_type(4)));
+typedef short i16x8_t __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+
+__device__ __forceinline__ void wd_dma_16(unsigned lds_addr, unsigned voff, const void *base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n"
+               :: "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
+}
+
+// eight consecutive positions of this lane's column: two transposing reads four rows apart
+__device__ __forceinline__ bf16x8_t wd_frag(const lds_byte_t *p) {
+  typedef __attribute__((address_space(3))) i16x4_t lds_i16x4_t;
+  const i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_t *)(p));
+  const i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_t *)(p + 4 * kWgBig * 2));
+  const i16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// MAP_A / MAP_B: the operand's rows are rows_x[position] (else the position itself)
+template <bool MAP_A, bool MAP_B>
+__global__ __launch_bounds__(512) void wgrad_bf16_dma_kernel(const bf16_t *__restrict__ A, int64_t lda, int M,
+                                                             const bf16_t *__restrict__ Bm, int64_t ldb, int N,
+                                                             const int32_t *__restrict__ rows_a,
+                                                             const int32_t *__restrict__ rows_b,
+                                                             const int32_t *__restrict__ offsets, int64_t n_pos,
+                                                             int n_groups, float *__restrict__ C) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char wd_smem[];
+  const int tn = N / kWgBig, tm = M / kWgBig;                      // (the launcher checks divisibility)
+  const int per_xcd = gridDim.x / 8;                             // tiles dealt to XCDs in contiguous runs
+  const int t = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (t >= tn * tm * n_groups) return;
+  const int e = t / (tn * tm);
+  const int64_t p_lo = offsets ? offsets[e] : 0, p_hi = offsets ? offsets[e + 1] : n_pos;
+  const int m0 = ((t / tn) % tm) * kWgBig, n0 = (t % tn) * kWgBig;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave & 3, wn = wave >> 2;                       // 4 x 2 waves, 64 x 128 each
+  f32x16_t acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+  const int frag_row = lane & 31, frag_half = lane >> 5;
+  const int64_t n_grp = p_hi - p_lo;
+  const int KT = static_cast<int>((n_grp + kWgSlab - 1) / kWgSlab);
+
+  if (KT > 0) {
+    const lds_byte_t *lds = (const lds_byte_t *)wd_smem;
+    const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) void *)wd_smem));
+    const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * (kWdInstr * 1024));
+
+    // DMA side: instruction j of a half slab fills rows 8 wave + 2 j and + 1 of the slot; this lane
+    // brings position lane & 31 of row 2 j + (lane >> 5), i.e. the chunk that belongs there
+    const int half = lane >> 5;
+    unsigned col_a[kWdInstr], col_b[kWdInstr];
+#pragma unroll
+    for (int j = 0; j < kWdInstr; ++j) {
+      const int r = 2 * j + half;                                 // (8 wave is a multiple of 4)
+      const unsigned c = static_cast<unsigned>((lane & 31) ^ (4 * (r & 3)));
+      col_a[j] = (static_cast<unsigned>(m0) + c * 8) * 2;
+      col_b[j] = (static_cast<unsigned>(n0) + c * 8) * 2;
+    }
+    const unsigned lda2 = static_cast<unsigned>(lda) * 2, ldb2 = static_cast<unsigned>(ldb) * 2;
+
+    // the eight operand rows a wave brings for half slab h (uniform: scalar loads)
+    auto row_idx = [&](int h, unsigned (&off)[8]) __attribute__((always_inline)) {
+      const int m = h >> 1, sl = m < KT ? m : KT - 1;             // past the end: harmless reload
+      const int64_t pb = p_lo + static_cast<int64_t>(sl) * kWgSlab + wave * 8;
+      const int32_t *rows = (h & 1) ? rows_b : rows_a;
+      const unsigned ld2 = (h & 1) ? ldb2 : lda2;
+      const bool mapped = (h & 1) ? MAP_B : MAP_A;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int64_t pp = pb + i < n_pos ? pb + i : n_pos - 1;
+        const unsigned r = mapped ? static_cast<unsigned>(rows[pp]) : static_cast<unsigned>(pp);
+        off[i] = r * ld2;                                         // (the launcher checks that this fits 32 bits)
+      }
+    };
+    auto issue = [&](int h, const unsigned (&off)[8]) __attribute__((always_inline)) {
+      const unsigned slot = lds_wave + static_cast<unsigned>(h % kWdSlots) * kWdSlotBytes;
+      const void *base = (h & 1) ? static_cast<const void *>(Bm) : static_cast<const void *>(A);
+#pragma unroll
+      for (int j = 0; j < kWdInstr; ++j) {
+        const unsigned voff = (half ? off[2 * j + 1] : off[2 * j]) + ((h & 1) ? col_b[j] : col_a[j]);
+        wd_dma_16(slot + j * 1024, voff, base);
+      }
+    };
+
+    // fragment side: lane i of a 16-lane group names row i >> 2 (of four), columns 4 (i & 3) .. + 3 of
+    // its group's 16 columns and receives column i; groups 0/1 hold tile rows 0-15 / 16-31 of
+    // positions 0-7, groups 2/3 the same of positions 8-15
+    const int i16 = lane & 15, grp = lane >> 4;
+    const int row_l = 8 * (grp >> 1) + (i16 >> 2);
+    const int sw = 4 * (i16 >> 2);
+    unsigned a_off[2], b_off[4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int chunk = (wm * 8 + i * 4 + 2 * (grp & 1) + ((i16 >> 1) & 1)) ^ sw;
+      a_off[i] = static_cast<unsigned>(row_l * (kWgBig * 2) + chunk * 16 + (i16 & 1) * 8);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int chunk = (wn * 16 + j * 4 + 2 * (grp & 1) + ((i16 >> 1) & 1)) ^ sw;
+      b_off[j] = static_cast<unsigned>(row_l * (kWgBig * 2) + chunk * 16 + (i16 & 1) * 8);
+    }
+    bf16x8_t fa0[2], fa1[2], fb0[4], fb1[4];
+    auto load_frags = [&](int m, int kk, bf16x8_t(&af)[2], bf16x8_t(&bfr)[4]) __attribute__((always_inline)) {
+      const lds_byte_t *sa = lds + ((2 * m) % kWdSlots) * kWdSlotBytes + kk * (16 * kWgBig * 2);
+      const lds_byte_t *sb = lds + ((2 * m + 1) % kWdSlots) * kWdSlotBytes + kk * (16 * kWgBig * 2);
+      af[0] = wd_frag(sa + a_off[0]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bfr[j] = wd_frag(sb + b_off[j]);
+      af[1] = wd_frag(sa + a_off[1]);
+    };
+    auto mma = [&](const bf16x8_t(&af)[2], const bf16x8_t(&bfr)[4]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+    };
+    // rows of slab m past the group's end, both operands; ends in a barrier
+    const int tail = static_cast<int>(n_grp % kWgSlab);
+    auto zero_tail = [&](int m) __attribute__((always_inline)) {
+      __attribute__((address_space(3))) unsigned char *sa =
+          (__attribute__((address_space(3))) unsigned char *)wd_smem + ((2 * m) % kWdSlots) * kWdSlotBytes;
+      __attribute__((address_space(3))) unsigned char *sb =
+          (__attribute__((address_space(3))) unsigned char *)wd_smem + ((2 * m + 1) % kWdSlots) * kWdSlotBytes;
+      const int first = tail * (kWgBig * 2), bytes = (kWgSlab - tail) * (kWgBig * 2);
+      for (int q = tid * 16; q < bytes; q += 512 * 16) {
+        *(__attribute__((address_space(3))) u32x4_t *)(sa + first + q) = u32x4_t{0u, 0u, 0u, 0u};
+        *(__attribute__((address_space(3))) u32x4_t *)(sb + first + q) = u32x4_t{0u, 0u, 0u, 0u};
+      }
+      __syncthreads();
+    };
+
+    {
+      unsigned off[kWdSlots][8];                                  // all index loads first: one round trip, not five
+#pragma unroll
+      for (int h = 0; h < kWdSlots; ++h) row_idx(h, off[h]);
+#pragma unroll
+      for (int h = 0; h < kWdSlots; ++h) issue(h, off[h]);
+    }
+    // slab 0 is in LDS once only A(1), B(1), A(2) are outstanding
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(3 * kWdInstr) : "memory");
+    if (tail != 0 && KT == 1) zero_tail(0);
+    load_frags(0, 0, fa0, fb0);
+
+    for (int m = 0; m < KT; ++m) {
+      unsigned off_b[8], off_a[8];
+      row_idx(2 * m + kWdSlots, off_b);                           // B(m+2) and A(m+3), issued after this slab
+      row_idx(2 * m + kWdSlots + 1, off_a);
+      load_frags(m, 1, fa1, fb1);
+      mma(fa0, fb0);
+      load_frags(m, 2, fa0, fb0);
+      mma(fa1, fb1);
+      load_frags(m, 3, fa1, fb1);
+      mma(fa0, fb0);
+      // slab m+1 has landed for everyone (only A(m+2) is outstanding) and nobody reads slab m any more
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kWdInstr) : "memory");
+      issue(2 * m + kWdSlots, off_b);                             // B(m+2) into the slot of A(m)
+      issue(2 * m + kWdSlots + 1, off_a);                         // A(m+3) into the slot of B(m)
+      if (tail != 0 && m + 2 == KT) zero_tail(m + 1);
+      load_frags(m + 1, 0, fa0, fb0);
+      mma(fa1, fb1);
+    }
+    // no DMA may be in flight into LDS that the next workgroup on this CU owns
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  }
+
+  // the B fragment is the MFMA's row operand: this lane holds, for output row m = frag_row, the
+  // columns 8 q + 4 frag_half + r of each 32-wide tile in accumulator element 4 q + r
+  float *Ce = C + static_cast<int64_t>(e) * M * N;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int m = m0 + wm * 64 + i * 32 + frag_row;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int cc = n0 + wn * 128 + j * 32 + q * 8 + frag_half * 4;
+        *reinterpret_cast<float4 *>(Ce + static_cast<int64_t>(m) * N + cc) =
+            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+      }
+  }
+}
+
 // rows scaled by a per-row factor (the gate weight of Eq. (12) on d_out):
 // dst[r, :] = scale[scale_idx ? scale_idx[r] : r] * src[src_idx ? src_idx[r] : r, :]
 // (top-K: r is a sorted position, src_idx its token, scale_idx its slot)
@@ -1277,6 +1487,38 @@ hipError_t launch_wgrad(int dtype, const void *A, int64_t lda, int M, const void
                         int n_groups, int64_t n_pos, float *C, hipStream_t s) {
   const bool mfma = dtype == ROM_DTYPE_BF16 && M % 8 == 0 && N % 8 == 0 && lda % 8 == 0 && ldb % 8 == 0 &&
                     reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(Bm) % 16 == 0;
+  if (mfma && !row_scale && M % kWgBig == 0 && N % kWgBig == 0 && M > 0 && N > 0 && n_pos > 0 && kUseWgradDma &&
+      static_cast<uint64_t>(n_pos) * static_cast<uint64_t>(lda) * 2 < (1ull << 32) &&
+      static_cast<uint64_t>(n_pos) * static_cast<uint64_t>(ldb) * 2 < (1ull << 32)) {
+    // (operand rows are rows_x[p] < n_pos or p itself: 32-bit byte offsets reach every one of them)
+    static std::mutex mu;
+    static std::atomic<bool> done[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!done[dev].load(std::memory_order_acquire)) {
+      std::lock_guard<std::mutex> lock(mu);
+      if (!done[dev].load(std::memory_order_relaxed)) {
+        const void *fns[4] = {reinterpret_cast<const void *>(&wgrad_bf16_dma_kernel<false, false>),
+                              reinterpret_cast<const void *>(&wgrad_bf16_dma_kernel<false, true>),
+                              reinterpret_cast<const void *>(&wgrad_bf16_dma_kernel<true, false>),
+                              reinterpret_cast<const void *>(&wgrad_bf16_dma_kernel<true, true>)};
+        for (const void *fn : fns) {
+          e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kWdSmem);
+          if (e != hipSuccess) return e;
+        }
+        done[dev].store(true, std::memory_order_release);
+      }
+    }
+    const int64_t tiles = static_cast<int64_t>(N / kWgBig) * (M / kWgBig) * n_groups;
+    const dim3 grid(static_cast<unsigned>(ceil_div(tiles, 8) * 8));
+    auto kernel = rows_a ? (rows_b ? &wgrad_bf16_dma_kernel<true, true> : &wgrad_bf16_dma_kernel<true, false>)
+                         : (rows_b ? &wgrad_bf16_dma_kernel<false, true> : &wgrad_bf16_dma_kernel<false, false>);
+    hipLaunchKernelGGL(kernel, grid, dim3(512), kWdSmem, s, static_cast<const bf16_t *>(A), lda, M,
+                       static_cast<const bf16_t *>(Bm), ldb, N, rows_a, rows_b, offsets, n_pos, n_groups, C);
+    return hipGetLastError();
+  }
   if (mfma && !row_scale && M >= kWgBig && N >= kWgBig) {
     // more than 64 KiB of dynamic LDS: a function attribute, set once per device
     static std::mutex mu;
