@@ -1369,18 +1369,19 @@ int backward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_
   float *d_gate = reinterpret_cast<float *>(at(bp.d_gate));
   float *d_logits = reinterpret_cast<float *>(at(bp.d_logits));
 
-  // transposed weights: d_inp = d_out W contracts over the row index of W
-  ROM_TRY(launch_transpose(d->dtype, w->w_out, at(bp.wt_out), E, Dm, De, s));          // -> [E][De][Dm]
+  // transposed weights: d_inp = d_out W contracts over the row index of W (the two big projections
+  // are transposed only where the GEMM cannot read them contraction-major, see dgrad)
   ROM_TRY(launch_transpose(d->dtype, w->w_dt, at(bp.wt_dt), Ex, De, R, s));            // -> [Ex][R][De]
   ROM_TRY(launch_transpose(d->dtype, w->w_x, at(bp.wt_x), Ex, R + 32, De, s));         // -> [Ex][De][R+32]
-  ROM_TRY(launch_transpose(d->dtype, w->w_in, at(bp.wt_in), E, 2 * De, Dm, s));        // -> [E][Dm][2De]
 
   // Input gradient of a routed projection, d_inp[n] = sum_k W[e_k(n)]^T d_outp[n]: the forward's grouped
   // GEMM on the transposed weights.  top-1: rows gathered from and scattered to token order, C is the
   // result.  top-K: A rows by token (or, a_by_pos, already one per sorted position), one output row per
   // sorted position in `pos`, then the K rows of a token are added (like the forward's per-slot outputs).
+  // W_fwd (optional): the forward weight [n_groups][k_in][n_out] that Wt is to be the transpose of.  Where
+  // the GEMM takes it contraction-major it is read as it is; otherwise it is transposed into Wt here.
   auto dgrad = [&](const void *A, int64_t lda, bool a_by_pos, const void *Wt, int n_groups, int n_out, int k_in, void *C,
-                   int64_t ldc, int c_is_f32, void *pos) -> int {
+                   int64_t ldc, int c_is_f32, void *pos, const void *W_fwd = nullptr) -> int {
     GemmArgs ga;
     memset(&ga, 0, sizeof(ga));
     ga.dtype = d->dtype;
@@ -1389,18 +1390,25 @@ int backward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_
     ga.ldc = ldc; ga.c_is_f32 = c_is_f32;
     if (n_groups <= 1) {
       ga.n_groups = 1; ga.M = N; ga.C = C;
-      ROM_TRY(launch_grouped_gemm(ga, s));
-      return ROM_OK;
+    } else {
+      ga.n_groups = n_groups; ga.offsets = offsets; ga.M = S;
+      ga.a_rows = a_by_pos ? nullptr : tok_of_pos;
+      if (!multi) {
+        ga.c_rows = tok_of_pos; ga.C = C;
+      } else {
+        ga.C = pos;
+      }
     }
-    ga.n_groups = n_groups; ga.offsets = offsets; ga.M = S;
-    ga.a_rows = a_by_pos ? nullptr : tok_of_pos;
-    if (!multi) {
-      ga.c_rows = tok_of_pos; ga.C = C;
-      ROM_TRY(launch_grouped_gemm(ga, s));
-      return ROM_OK;
+    if (W_fwd) {
+      GemmArgs gk = ga;
+      gk.W = W_fwd; gk.w_kmajor = 1;
+      if (grouped_gemm_takes_kmajor(gk))
+        ga = gk;
+      else
+        ROM_TRY(launch_transpose(d->dtype, W_fwd, const_cast<void *>(Wt), n_groups < 1 ? 1 : n_groups, k_in, n_out, s));
     }
-    ga.C = pos;
     ROM_TRY(launch_grouped_gemm(ga, s));
+    if (n_groups <= 1 || !multi) return ROM_OK;
     const bool f32 = c_is_f32 || eb == 4;
     ROM_TRY(launch_slot_sum(f32, f32, pos, ldc, C, ldc, inv_perm, N, K, n_out, nullptr, 0, nullptr, s));
     return ROM_OK;
@@ -1424,7 +1432,7 @@ int backward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_
   const void *dsc;            // gate-weighted d_out, one row per sorted position
   const float *scan_gate;     // weight the adjoint scan still has to put on d g
   if (!multi) {
-    ROM_RC(dgrad(d_out, Dm, false, at(bp.wt_out), E, De, Dm, at(bp.dg_raw), De, 0, nullptr));   // dg_raw = W_out[e]^T d_out
+    ROM_RC(dgrad(d_out, Dm, false, at(bp.wt_out), E, De, Dm, at(bp.dg_raw), De, 0, nullptr, w->w_out));   // dg_raw = W_out[e]^T d_out
     ROM_TRY(launch_gate_backward(d->dtype, at(bp.dg_raw), at(p.g), nullptr, 1, N, De, d_gate, s));
     // (the gate weight goes onto d_out once, in the buffer that later receives dx_in, so that the
     // weight-gradient kernel contracts two plain operands)
@@ -1437,7 +1445,7 @@ int backward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_
     ROM_TRY(launch_scale_rows(d->dtype, d_out, gate, tok_of_pos, perm, S, Dm, at(bp.pos_dm), s));
     dsc = at(bp.pos_dm);
     ROM_TRY(wgrad(dsc, Dm, true, Dm, at(p.g), De, De, E, gr->d_w_out));
-    ROM_RC(dgrad(dsc, Dm, true, at(bp.wt_out), E, De, Dm, at(bp.dg_raw), De, 0, at(bp.pos_de)));   // already gate-weighted
+    ROM_RC(dgrad(dsc, Dm, true, at(bp.wt_out), E, De, Dm, at(bp.dg_raw), De, 0, at(bp.pos_de), w->w_out));   // already gate-weighted
     scan_gate = nullptr;
   }
   // Eq. (5), (6): scan, gate, softplus
@@ -1463,7 +1471,7 @@ int backward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_
                                gr->d_conv_b, s));
   // Eq. (10)/(11): in / gate projection
   ROM_RC(dgrad(at(bp.d_xz), 2 * De, false, at(bp.wt_in), E, Dm, 2 * De, at(bp.dx_in), Dm, 0,
-               multi ? at(bp.pos_dm) : nullptr));
+               multi ? at(bp.pos_dm) : nullptr, w->w_in));
   ROM_TRY(wgrad(at(bp.d_xz), 2 * De, false, 2 * De, x, Dm, Dm, E, gr->d_w_in));
 #undef ROM_RC
   // Eq. (9): the router through the gate weights

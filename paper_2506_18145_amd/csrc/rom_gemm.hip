@@ -561,7 +561,13 @@ __device__ __forceinline__ void dma_load_16(unsigned lds_addr, unsigned voff, co
 // BN < 256 (a single, narrow column tile: the x projection) keeps the 256-row activation tile and
 // the five 32 KiB ring slots; the weight half slabs just fill less of theirs.  grid.y slices the
 // inner dimension (fp32 partial sums, plain epilogue only).
-template <int BN, int WM, int WN, int EPI>
+// WT: the weight is stored contraction-major, [group][K][N] (a forward weight used for the input
+// gradient without a transposed copy; BN = 256, N a multiple of 256).  Its half slab is then 64
+// contraction rows x 256 output columns as they lie in memory, two rows per DMA instruction, chunk c
+// of row r at position c ^ 4 (r & 3), and the MFMA fragments - eight consecutive contraction indices of
+// one output column per lane - come out of it through the transposing LDS read (ds_read_b64_tr_b16:
+// the 16 lanes of a group name four rows x 16 columns, lane i receives column i of the four rows).
+template <int BN, int WM, int WN, int EPI, bool WT = false>
 __device__ __forceinline__ void dma_tile(const GemmArgs &a, const TileCoord &tc, uint4 *smem) {
   constexpr int BM = 256, NW = WM * WN;
   static_assert(kDmaSlots == 4 || kDmaSlots == 5, "ring of four or five half-slab slots");
@@ -571,13 +577,15 @@ __device__ __forceinline__ void dma_tile(const GemmArgs &a, const TileCoord &tc,
   constexpr int kSlotBytes = kSlotChunks * 16;                // 32 KiB
   constexpr int kAInstr = BM / (8 * NW);                      // DMA instructions per wave and half slab: 8 rows each
   constexpr int kWInstr = (BN + 8 * NW - 1) / (8 * NW);       // (rows past BN are clamped re-reads into unused slot space)
+  static_assert(!WT || (BN == 256 && NW == 8), "contraction-major weights: the 256 x 256 tile on eight waves");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
   const int k_begin = blockIdx.y * a.k_per_split;
   const int k_len = (a.K - k_begin < a.k_per_split) ? a.K - k_begin : a.k_per_split;
   const bf16_t *Ap = static_cast<const bf16_t *>(a.A) + k_begin;
-  const bf16_t *Wp = static_cast<const bf16_t *>(a.W) + static_cast<int64_t>(tc.group) * a.N * a.K + k_begin;
+  const bf16_t *Wp = static_cast<const bf16_t *>(a.W) + static_cast<int64_t>(tc.group) * a.N * a.K +
+                     (WT ? static_cast<int64_t>(k_begin) * a.N : k_begin);
 
   // this lane's share of a half slab: one 16-byte chunk in each of its wave's 8-row groups
   unsigned a_voff[kAInstr], b_voff[kWInstr];
@@ -591,10 +599,16 @@ __device__ __forceinline__ void dma_tile(const GemmArgs &a, const TileCoord &tc,
   }
 #pragma unroll
   for (int j = 0; j < kWInstr; ++j) {
-    const int r = (wave * kWInstr + j) * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ ((r >> 1) & 7);
-    const int n = (tc.n0 + r < a.N) ? tc.n0 + r : a.N - 1;
-    b_voff[j] = static_cast<unsigned>((static_cast<int64_t>(n) * a.K + c * 8) * 2);
+    if constexpr (WT) {
+      const int r = (wave * kWInstr + j) * 2 + (lane >> 5);    // contraction row within the slab
+      const int c = (lane & 31) ^ (4 * (r & 3));
+      b_voff[j] = static_cast<unsigned>((static_cast<int64_t>(r) * a.N + tc.n0 + c * 8) * 2);
+    } else {
+      const int r = (wave * kWInstr + j) * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ ((r >> 1) & 7);
+      const int n = (tc.n0 + r < a.N) ? tc.n0 + r : a.N - 1;
+      b_voff[j] = static_cast<unsigned>((static_cast<int64_t>(n) * a.K + c * 8) * 2);
+    }
   }
   const unsigned lds_base =
       static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) void *)smem));
@@ -608,7 +622,7 @@ __device__ __forceinline__ void dma_tile(const GemmArgs &a, const TileCoord &tc,
     const int sl = m < KT ? m : KT - 1;                        // past the end: harmless reload
     const unsigned slot = static_cast<unsigned>(h % kDmaSlots) * kSlotBytes;
     if (h & 1) {
-      const bf16_t *wb = Wp + sl * kDmaBK;
+      const bf16_t *wb = Wp + (WT ? static_cast<int64_t>(sl) * kDmaBK * a.N : static_cast<int64_t>(sl) * kDmaBK);
 #pragma unroll
       for (int j = 0; j < kWInstr; ++j) dma_load_16(lds_wave_w + slot + j * 1024, b_voff[j], wb);
     } else {
@@ -629,6 +643,16 @@ __device__ __forceinline__ void dma_tile(const GemmArgs &a, const TileCoord &tc,
   const int frag_row = lane & 31, frag_half = lane >> 5;
   const int a_base = (wm * WTM + frag_row) * kDmaRC, b_base = (wn * WTN + frag_row) * kDmaRC;
   const int swz = (frag_row >> 1) & 7;
+  // contraction-major W: byte offset of this lane's 8 bytes in the first of its two 4-row reads
+  unsigned wt_off[TN];
+  if constexpr (WT) {
+    const int i16 = lane & 15, grp = lane >> 4;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int chunk = (wn * (WTN / 8) + j * 4 + 2 * (grp & 1) + ((i16 >> 1) & 1)) ^ (4 * (i16 >> 2));
+      wt_off[j] = static_cast<unsigned>((8 * (grp >> 1) + (i16 >> 2)) * 512 + chunk * 16 + (i16 & 1) * 8);
+    }
+  }
   bf16x8_t fa0[TM], fa1[TM], fb0[TN], fb1[TN];
   auto load_frags = [&](int m, int kk, bf16x8_t(&af)[TM], bf16x8_t(&bfr)[TN]) __attribute__((always_inline)) {
     const int c = (kk * 2 + frag_half) ^ swz;
@@ -640,8 +664,19 @@ __device__ __forceinline__ void dma_tile(const GemmArgs &a, const TileCoord &tc,
     }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const uint4 v = sb[b_base + j * 32 * kDmaRC + c];
-      bfr[j] = *reinterpret_cast<const bf16x8_t *>(&v);
+      if constexpr (WT) {
+        typedef short i16x4_t __attribute__((ext_vector_type(4)));
+        typedef short i16x8_t __attribute__((ext_vector_type(8)));
+        typedef __attribute__((address_space(3))) i16x4_t lds_i16x4_t;
+        const __attribute__((address_space(3))) unsigned char *pb =
+            (const __attribute__((address_space(3))) unsigned char *)sb + kk * (16 * 512) + wt_off[j];
+        const i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_t *)pb);
+        const i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_t *)(pb + 4 * 512));
+        bfr[j] = __builtin_bit_cast(bf16x8_t, (i16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      } else {
+        const uint4 v = sb[b_base + j * 32 * kDmaRC + c];
+        bfr[j] = *reinterpret_cast<const bf16x8_t *>(&v);
+      }
     }
 #pragma unroll
     for (int i = 1; i < TM; ++i) {
@@ -682,12 +717,12 @@ __device__ __forceinline__ void dma_tile(const GemmArgs &a, const TileCoord &tc,
   mfma_epilogue<EPI, TM, TN, WTM, WTN>(a, tc, acc, smem, wave, wm, wn, lane);
 }
 
-template <int BN, int WM, int WN, int EPI>
+template <int BN, int WM, int WN, int EPI, bool WT = false>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_dma_kernel(const GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint4 smem[];
   const TileCoord tc = locate_tile(a, 256, BN);
   if (!tc.valid) return;
-  dma_tile<BN, WM, WN, EPI>(a, tc, smem);
+  dma_tile<BN, WM, WN, EPI, WT>(a, tc, smem);
 }
 
 // ------------------------------------------------------------------ bf16 MFMA kernel, short inner dimension
@@ -933,13 +968,13 @@ bool smallk_takes(const GemmArgs &a) {
          !a.row_scale && !a.c_is_f32;
 }
 
-template <int BN, int WM, int WN, int EPI>
+template <int BN, int WM, int WN, int EPI, bool WT = false>
 hipError_t launch_dma(const GemmArgs &a, hipStream_t s) {
   constexpr int kSmem = kDmaSlots * 256 * kDmaRC * 16;     // 160 KiB
   static LdsAttrOnce attr;
-  const hipError_t e = attr.ensure(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<BN, WM, WN, EPI>), kSmem);
+  const hipError_t e = attr.ensure(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<BN, WM, WN, EPI, WT>), kSmem);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((gemm_bf16_dma_kernel<BN, WM, WN, EPI>), dim3(grid_tiles(a, 256, BN), a.k_splits),
+  hipLaunchKernelGGL((gemm_bf16_dma_kernel<BN, WM, WN, EPI, WT>), dim3(grid_tiles(a, 256, BN), a.k_splits),
                      dim3(WM * WN * 64), kSmem, s, a);
   return hipGetLastError();
 }
@@ -970,6 +1005,17 @@ hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
 
 }  // namespace
 
+// whether a call with a contraction-major weight (GemmArgs::w_kmajor) is taken: the 256 x 256 DMA tile with a
+// plain epilogue only; the caller otherwise makes a transposed copy of the weight
+bool grouped_gemm_takes_kmajor(const GemmArgs &args) {
+  GemmArgs a = args;
+  a.k_splits = 1;
+  a.k_per_split = static_cast<int>(ceil_div(a.K, 64) * 64);
+  const int64_t rows_per_group = a.M / (a.n_groups > 0 ? a.n_groups : 1);
+  return grouped_gemm_on_mfma(a) && !a.c_is_f32 && !a.bias && !a.row_scale && !a.residual && !a.swiglu &&
+         rows_per_group >= 1024 && a.N % 256 == 0 && a.K > 256 && dma_ok(a);
+}
+
 // whether the call takes the MFMA kernels (else the plain FMA kernel, which has no fused SwiGLU)
 bool grouped_gemm_on_mfma(const GemmArgs &a) {
   const int out_align = a.c_is_f32 ? 4 : 8;      // elements per output store
@@ -991,6 +1037,10 @@ hipError_t launch_grouped_gemm(const GemmArgs &args, hipStream_t s) {
   a.k_per_split = static_cast<int>(ceil_div(ceil_div(a.K, a.k_splits), 64) * 64);
   a.k_splits = static_cast<int>(ceil_div(a.K, a.k_per_split));
   const bool mfma_ok = grouped_gemm_on_mfma(a);
+  if (a.w_kmajor) {                                           // the caller asks grouped_gemm_takes_kmajor first
+    if (!grouped_gemm_takes_kmajor(args)) return hipErrorInvalidValue;
+    return launch_dma<256, kBigWM, kBigWN, kEpiPlain, true>(a, s);
+  }
   if (a.swiglu && !mfma_ok) return hipErrorInvalidValue;      // the caller asks grouped_gemm_on_mfma first
   if (a.swiglu) return launch_mfma_tiles<kEpiSwiGLU>(a, s);
   if (!mfma_ok) {

@@ -88,6 +88,8 @@ struct GemmArgs {
   const void *residual;      // type T, laid out like C (row c_row, pitch ldc), or NULL: added after the row scale
   int swiglu;                // 1: W's rows are blocks of 8 gate + 8 up features; C [*, N/2] = SiLU(gate) * up
                              // (after the row scale); MFMA kernels only, see grouped_gemm_on_mfma
+  int w_kmajor;              // 1: W is [n_groups, K, N] row-major (contraction-major); only where
+                             // grouped_gemm_takes_kmajor says so
   int no_xcd_remap;          // set by the launcher: logical tile = workgroup id (no contiguous run per XCD)
   int k_splits;              // > 1: slice the inner dimension; slice s writes its partial sums (fp32, plain
                              // epilogue only) to C + s * c_split_stride; the consumer adds the slices up
@@ -96,6 +98,7 @@ struct GemmArgs {
 };
 hipError_t launch_grouped_gemm(const GemmArgs &a, hipStream_t s);
 bool grouped_gemm_on_mfma(const GemmArgs &a);
+bool grouped_gemm_takes_kmajor(const GemmArgs &a);
 
 // ---------------------------------------------------------------- sequence kernels
 // sum over the K slots of a token: dst[n, :] = act(row_scale[n] * sum_k src[inv_perm[n*K+k], :] + bias)
