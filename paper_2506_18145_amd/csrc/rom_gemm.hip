@@ -550,6 +550,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
 constexpr int kDmaBK = 64, kDmaRC = kDmaBK / 8, kDmaSlots = 5;
 constexpr bool kUseDma = true;
 constexpr int kSkinnyMinWgs = 100;
+constexpr int kSkinnyColsMaxWgs = 200;    // fewer 64 x 128 tiles than this: 64 x 64 tiles instead
 constexpr bool kUseSmallK = true;
 constexpr int kBigWM = 4, kBigWN = 2;     // wave layout of the 256x256 DMA tile
 
@@ -1000,6 +1001,10 @@ hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
   // few XCDs.  Deal the tiles round-robin instead.
   GemmArgs spread = a;
   spread.no_xcd_remap = 1;
+  // a narrow output (the step's out projection: 8 experts x 16 column tiles) leaves half of the CUs
+  // without a workgroup while the weights stream past once: halve the column tile
+  const int64_t row_tiles = (a.n_groups > 0 ? a.n_groups : 1) * ceil_div(rows_per_group > 0 ? rows_per_group : 1, 64);
+  if (row_tiles * ceil_div(a.N, 128) < kSkinnyColsMaxWgs && a.N % 64 == 0) return launch_mfma<64, 64, 2, 2, EPI>(spread, s);
   return launch_mfma<64, 128, 2, 2, EPI>(spread, s);
 }
 
