@@ -558,3 +558,32 @@ def rom_layer_backward(x, w, top_k, gate_mode, d_out, expert_idx=None):
         "d_g": d_g, "d_y": d_y, "d_z": d_z, "d_dt": d_dt, "d_pre": d_pre, "d_u": d_u, "d_u_scan": sc["d_u"].reshape(n_tok, d_e),
         "d_xdbl": d_xdbl, "d_xz": d_xz, "d_gate": d_gate, "d_logits": d_logits, "fwd": fwd,
     }
+
+
+def rms_norm_backward(x, weight, eps, d_y):
+    """Adjoint of rms_norm: y = x / sqrt(mean(x^2) + eps) * weight.  With r = 1 / sqrt(mean(x^2) + eps)
+    and x^ = x r:  d_weight = sum over rows of d_y x^;  d_x = r (d_y weight - x^ mean_d(d_y weight x^)).
+    Returns (d_x, d_weight)."""
+    x = np.asarray(x, F64)
+    d_y = np.asarray(d_y, F64)
+    wgt = np.asarray(weight, F64)
+    r = 1.0 / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps)
+    xh = x * r
+    d_weight = (d_y * xh).reshape(-1, x.shape[-1]).sum(axis=0)
+    d_xh = d_y * wgt
+    d_x = r * (d_xh - xh * np.mean(d_xh * xh, axis=-1, keepdims=True))
+    return d_x, d_weight
+
+
+def rom_block_backward(x, w, top_k, gate_mode, d_out, eps=1e-5, expert_idx=None):
+    """Gradients of rom_block_forward (zero initial states): the layer's backward on the normalised
+    input, the norm's adjoint, and the skip connection's d_out added to d_x.  Returns the dict of
+    rom_layer_backward with d_x the block's input gradient and d_norm_w [D_m] added."""
+    x = np.asarray(x, F64)
+    xn = rms_norm(x, w["norm_w"], eps)
+    res = rom_layer_backward(xn, w, top_k, gate_mode, d_out, expert_idx)
+    d_x_norm, d_norm_w = rms_norm_backward(x, w["norm_w"], eps, res["d_x"])
+    res["d_xn"] = res["d_x"]
+    res["d_x"] = np.asarray(d_out, F64) + d_x_norm
+    res["d_norm_w"] = d_norm_w
+    return res

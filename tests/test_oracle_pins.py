@@ -783,6 +783,63 @@ def test_backward_matches_central_differences_of_the_forward_oracle():
             assert abs(fd - grad[i]) <= 1e-6 * scale + 1e-8, (name, i, fd, grad[i])
 
 
+def test_rms_norm_backward_against_library_differentiation():
+    rng = np.random.default_rng(31)
+    x = rng.standard_normal((3, 5, 12))
+    wgt = 1.0 + 0.3 * rng.standard_normal(12)
+    d_y = rng.standard_normal(x.shape)
+    d_x, d_w = O.rms_norm_backward(x, wgt, 1e-5, d_y)
+    tx = torch.tensor(x, requires_grad=True)
+    tw = torch.tensor(wgt, requires_grad=True)
+    y = F.rms_norm(tx, (12,), tw, 1e-5)
+    assert np.allclose(y.detach().numpy(), O.rms_norm(x, wgt, 1e-5), rtol=1e-12, atol=1e-14)
+    (y * torch.tensor(d_y)).sum().backward()
+    assert np.allclose(d_x, tx.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(d_w, tw.grad.numpy(), rtol=1e-10, atol=1e-12)
+    # the gradient has no component along x^ scaled by the weight-free norm: d_x . x = 0 when weight = 1
+    d_x1, _ = O.rms_norm_backward(x, np.ones(12), 0.0, d_y)
+    assert np.max(np.abs((d_x1 * x).sum(-1))) < 1e-12
+
+
+def test_block_backward_matches_central_differences_of_the_block_forward():
+    """out = x + RoM(RMSNorm(x)): d/d theta of sum(out * d_out) by central differences of
+    rom_block_forward at a fixed expert choice, for sampled entries of x, of the norm's scale and of
+    every parameter; and the skip alone (all-zero out projection) passes d_out through."""
+    cfg = tiny_cfg(top_k=2, gate_mode=1, n_experts=4, seq_len=7)
+    w = {k: (None if v is None else np.asarray(v, np.float64)) for k, v in _weights(cfg).items()}
+    rng = np.random.default_rng(29)
+    w["norm_w"] = 1.0 + 0.3 * rng.standard_normal(cfg.d_model)
+    x = 1.7 * np.asarray(make_input(cfg), np.float64)
+    d_out = rng.standard_normal(x.shape)
+    res = O.rom_block_backward(x, w, 2, 1, d_out, 1e-5)
+    idx = res["fwd"]["expert_idx"]
+    assert np.array_equal(idx, O.rom_block_forward(x, w, 2, 1, 1e-5)["expert_idx"])
+
+    def loss(xx, ww):
+        return float((O.rom_block_forward(xx, ww, 2, 1, 1e-5, expert_idx=idx)["out"] * d_out).sum())
+
+    eps = 1e-5
+    for name in _PARAMS + ("norm_w", "x"):
+        base = x if name == "x" else w[name]
+        grad = res["d_" + name]
+        assert grad.shape == base.shape, name
+        scale = np.max(np.abs(grad))
+        assert scale > 1e-6, name
+        for _ in range(8):
+            i = tuple(int(rng.integers(0, n)) for n in base.shape)
+            plus, minus = base.copy(), base.copy()
+            plus[i] += eps
+            minus[i] -= eps
+            if name == "x":
+                fd = (loss(plus, w) - loss(minus, w)) / (2 * eps)
+            else:
+                fd = (loss(x, dict(w, **{name: plus})) - loss(x, dict(w, **{name: minus}))) / (2 * eps)
+            assert abs(fd - grad[i]) <= 1e-6 * scale + 1e-8, (name, i, fd, grad[i])
+    w0 = dict(w, w_out=np.zeros_like(w["w_out"]))
+    res0 = O.rom_block_backward(x, w0, 2, 1, d_out, 1e-5, expert_idx=idx)
+    assert np.array_equal(res0["d_x"], d_out) and np.max(np.abs(res0["d_norm_w"])) == 0.0
+
+
 def test_scan_backward_closed_forms():
     """Constant coefficients: y_T depends on u_s through C . a^(T-s) . dt B (+ D at s = T), so a
     one-hot d_y at time T gives that as d_u; and the adjoint state after the last step back is
