@@ -118,6 +118,11 @@ def load_library() -> ctypes.CDLL:
     lib.rom_step_static.restype = ctypes.c_int
     lib.rom_step_static.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, I64, P, P, P, P]
     F32 = ctypes.c_float
+    lib.rom_block_backward_workspace_bytes.restype = SZ
+    lib.rom_block_backward_workspace_bytes.argtypes = [ctypes.POINTER(RomDims), I64, I64]
+    lib.rom_block_backward.restype = ctypes.c_int
+    lib.rom_block_backward.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, F32, P, I64, I64, P, P,
+                                       ctypes.POINTER(_RomGrads), P, P, SZ, P]
     lib.rom_fold_norm.restype = ctypes.c_int
     lib.rom_fold_norm.argtypes = [ctypes.POINTER(RomDims), P, P, P, P]
     lib.rom_block_forward.restype = ctypes.c_int
@@ -286,6 +291,21 @@ def rom_layer_backward(dims, weights, x, B, L, d_out, d_x, grads, ws, saved=Fals
     code = fn(ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(x), B, L, _ptr(d_out), _ptr(d_x),
               ctypes.byref(gs), _ptr(ws), _nbytes(ws), _stream())
     _check(code, "rom_layer_backward_saved" if saved else "rom_layer_backward")
+
+
+def rom_block_backward_workspace_bytes(dims: RomDims, B: int, L: int) -> int:
+    return int(load_library().rom_block_backward_workspace_bytes(ctypes.byref(dims), B, L))
+
+
+def rom_block_backward(dims, weights, norm_weight, eps, x, B, L, d_out, d_x, grads, d_norm_weight, ws):
+    """weights: the plain ones (w_in not folded); grads as for rom_layer_backward."""
+    gs = _RomGrads()
+    for name, _ in _RomGrads._fields_:
+        setattr(gs, name, _ptr(grads.get(name)))
+    code = load_library().rom_block_backward(
+        ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(norm_weight), eps, _ptr(x), B, L, _ptr(d_out),
+        _ptr(d_x), ctypes.byref(gs), _ptr(d_norm_weight), _ptr(ws), _nbytes(ws), _stream())
+    _check(code, "rom_block_backward")
 
 
 def _nbytes(t) -> int:
@@ -517,6 +537,7 @@ class RomLayer:
         self._ws: Optional[torch.Tensor] = None
         self._route_ws: Optional[torch.Tensor] = None
         self._bwd_ws: Optional[torch.Tensor] = None
+        self._blk_bwd_ws: Optional[torch.Tensor] = None
         self._block_weights: Optional[Dict[str, Optional[torch.Tensor]]] = None
 
     def block_weights(self, in_place: bool = False) -> Dict[str, Optional[torch.Tensor]]:
@@ -670,6 +691,34 @@ class RomLayer:
                 grads[name] = torch.empty(wt.shape, dtype=torch.float32, device=self.device)
         rom_layer_backward(self.dims, self.weights, x, B, L, d_out, d_x, grads, self._bwd_ws, saved=saved)
         return d_x, grads
+
+    def block_backward(self, x: torch.Tensor, d_out: torch.Tensor, eps: float = 1e-5):
+        """(d_x, grads) of the pre-norm residual block out = x + layer(RMSNorm(x)); grads also holds
+        d_norm_w.  Uses the plain weights (the fold of block_weights() is the forward's business)."""
+        B, L, _ = x.shape
+        need = rom_block_backward_workspace_bytes(self.dims, max(B, 1), max(L, 1))
+        if need == 0:
+            raise RomError("rom_block_backward_workspace_bytes returned 0: unsupported dims")
+        if self._blk_bwd_ws is None or self._blk_bwd_ws.numel() < need:
+            self._blk_bwd_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        d_x = torch.empty_like(x)
+        grads = {}
+        for name, _ in _RomGrads._fields_:
+            wt = self.weights.get(name[2:])
+            if wt is not None:
+                grads[name] = torch.empty(wt.shape, dtype=torch.float32, device=self.device)
+        grads["d_norm_w"] = torch.empty(self.dims.d_model, dtype=torch.float32, device=self.device)
+        rom_block_backward(self.dims, self.weights, self.weights["norm_w"], eps, x, B, L, d_out, d_x, grads,
+                           grads["d_norm_w"], self._blk_bwd_ws)
+        return d_x, grads
+
+    def block_backward_xn(self, B: int, L: int) -> torch.Tensor:
+        """The normalised input the last block_backward(B, L) call materialised (it follows the layer's
+        backward plan in the workspace, 256-byte aligned)."""
+        off = (rom_backward_workspace_bytes(self.dims, B, L) + 255) // 256 * 256
+        n = B * L * self.dims.d_model
+        nbytes = n * torch.empty((), dtype=self.tdtype).element_size()
+        return self._blk_bwd_ws[off:off + nbytes].view(self.tdtype).view(B, L, self.dims.d_model)
 
 
 class RomStack:

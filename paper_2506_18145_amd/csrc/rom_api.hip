@@ -1327,6 +1327,67 @@ int rom_layer_backward_saved(const rom_dims *d, const rom_weights *w, const void
 }
 
 namespace {
+// workspace of rom_block_backward: the layer's backward plan, then the normalised input, its gradient,
+// 1/rms per token and the partial sums of d_norm_weight
+struct BlockBwdPlan {
+  size_t total, inner, xn, d_xn, rstd, part;
+};
+BlockBwdPlan make_block_bwd_plan(const rom_dims *d, int64_t B, int64_t L) {
+  BlockBwdPlan p;
+  const size_t N = static_cast<size_t>(B) * static_cast<size_t>(L);
+  const size_t eb = d->dtype == ROM_DTYPE_BF16 ? 2 : 4;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off += (bytes + kAlign - 1) / kAlign * kAlign;
+    return at;
+  };
+  p.inner = make_bwd_plan(d, B, L).total;
+  take(p.inner);
+  p.xn = take(N * d->d_model * eb);
+  p.d_xn = take(N * d->d_model * eb);
+  p.rstd = take(N * 4);
+  p.part = take(static_cast<size_t>(rmsnorm_wgrad_parts(static_cast<int64_t>(N))) * d->d_model * 4);
+  p.total = off;
+  return p;
+}
+}  // namespace
+
+size_t rom_block_backward_workspace_bytes(const rom_dims *d, int64_t B, int64_t L) {
+  if (check_dims(d) != ROM_OK || B < 0 || L < 0) return 0;
+  if (rom_backward_workspace_bytes(d, B, L) == 0 && B > 0 && L > 0) return 0;
+  return make_block_bwd_plan(d, B, L).total;
+}
+
+int rom_block_backward(const rom_dims *d, const rom_weights *w, const float *norm_weight, float eps, const void *x,
+                       int64_t B, int64_t L, const void *d_out, void *d_x, const rom_grads *gr, float *d_norm_weight,
+                       void *ws, size_t ws_bytes, void *hip_stream) {
+  int rc = check_dims(d);
+  if (rc != ROM_OK) return rc;
+  if (!norm_weight || !aligned16(norm_weight) || !(eps >= 0.0f) || !d_norm_weight) return ROM_E_INVAL;
+  if (B < 0 || L < 0) return ROM_E_INVAL;
+  if (B == 0 || L == 0) return ROM_OK;
+  if (!x || !d_out || !d_x || !ws || d_x == x || d_x == d_out || !aligned16(x) || !aligned16(d_out) || !aligned16(d_x) ||
+      (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0)
+    return ROM_E_INVAL;
+  if (d->d_model % 4 != 0) return ROM_E_UNSUPPORTED;
+  const BlockBwdPlan p = make_block_bwd_plan(d, B, L);
+  if (ws_bytes < p.total) return ROM_E_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char *base = static_cast<char *>(ws);
+  const int64_t N = B * L;
+  float *rstd = reinterpret_cast<float *>(base + p.rstd);
+  // the layer's backward runs on the materialised norm (the forward block never forms it: its in
+  // projection scales rows of x W'^T instead, which differs by the rounding of xn to the type)
+  ROM_TRY(launch_rmsnorm_forward(d->dtype, x, norm_weight, eps, N, d->d_model, base + p.xn, rstd, s));
+  rc = backward_impl(d, w, base + p.xn, B, L, d_out, base + p.d_xn, gr, ws, p.inner, hip_stream, true);
+  if (rc != ROM_OK) return rc;
+  ROM_TRY(launch_rmsnorm_backward(d->dtype, x, norm_weight, rstd, base + p.d_xn, d_out, N, d->d_model, d_x,
+                                  reinterpret_cast<float *>(base + p.part), d_norm_weight, s));
+  return ROM_OK;
+}
+
+namespace {
 int backward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t B, int64_t L, const void *d_out,
                   void *d_x, const rom_grads *gr, void *ws, size_t ws_bytes, void *hip_stream, bool recompute) {
   int rc = check_dims(d);

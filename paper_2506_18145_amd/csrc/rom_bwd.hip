@@ -1482,6 +1482,148 @@ hipError_t launch_scale_rows(int dtype, const void *src, const float *scale, con
   return hipGetLastError();
 }
 
+namespace {
+// ---- RMS norm of the pre-norm block, forward (materialised for the backward pass) and adjoint
+// One wavefront per token row.  xn = x r norm_w, r = 1 / sqrt(mean(x^2) + eps), r kept per token.
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T *__restrict__ x, const float *__restrict__ norm_w,
+                                                          float eps, int64_t n_rows, int d_model, T *__restrict__ xn,
+                                                          float *__restrict__ rstd) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (row >= n_rows) return;
+  const T *xr = x + row * d_model;
+  float ss = 0.0f;
+  for (int c = lane * 4; c < d_model; c += 256) {
+    float v[4];
+    bwd_load4(xr + c, v);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) ss = fmaf(v[q], v[q], ss);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+  const float r = 1.0f / sqrtf(ss / static_cast<float>(d_model) + eps);
+  if (lane == 0) rstd[row] = r;
+  for (int c = lane * 4; c < d_model; c += 256) {
+    float v[4];
+    bwd_load4(xr + c, v);
+    const float4 g = *reinterpret_cast<const float4 *>(norm_w + c);
+    v[0] *= r * g.x; v[1] *= r * g.y; v[2] *= r * g.z; v[3] *= r * g.w;
+    bwd_store4(xn + row * d_model + c, v);
+  }
+}
+
+// d_x = d_skip + r (d_xn norm_w - x^ mean_d(d_xn norm_w x^)),  x^ = x r
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T *__restrict__ x, const float *__restrict__ norm_w,
+                                                          const float *__restrict__ rstd, const T *__restrict__ d_xn,
+                                                          const T *__restrict__ d_skip, int64_t n_rows, int d_model,
+                                                          T *__restrict__ d_x) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (row >= n_rows) return;
+  const T *xr = x + row * d_model, *dr = d_xn + row * d_model;
+  const float r = rstd[row];
+  float dot = 0.0f;
+  for (int c = lane * 4; c < d_model; c += 256) {
+    float v[4], dv[4];
+    bwd_load4(xr + c, v);
+    bwd_load4(dr + c, dv);
+    const float4 g = *reinterpret_cast<const float4 *>(norm_w + c);
+    dot = fmaf(dv[0] * g.x, v[0] * r, dot);
+    dot = fmaf(dv[1] * g.y, v[1] * r, dot);
+    dot = fmaf(dv[2] * g.z, v[2] * r, dot);
+    dot = fmaf(dv[3] * g.w, v[3] * r, dot);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+  const float m = dot / static_cast<float>(d_model);
+  for (int c = lane * 4; c < d_model; c += 256) {
+    float v[4], dv[4], sk[4], o[4];
+    bwd_load4(xr + c, v);
+    bwd_load4(dr + c, dv);
+    bwd_load4(d_skip + row * d_model + c, sk);
+    const float4 g = *reinterpret_cast<const float4 *>(norm_w + c);
+    o[0] = sk[0] + r * (dv[0] * g.x - v[0] * r * m);
+    o[1] = sk[1] + r * (dv[1] * g.y - v[1] * r * m);
+    o[2] = sk[2] + r * (dv[2] * g.z - v[2] * r * m);
+    o[3] = sk[3] + r * (dv[3] * g.w - v[3] * r * m);
+    bwd_store4(d_x + row * d_model + c, o);
+  }
+}
+
+// d_norm_w partials: part[blockIdx.y][c] = sum over the block's rows of d_xn[n, c] x[n, c] r[n]; thread = column
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_wgrad_partial_kernel(const T *__restrict__ x,
+                                                                    const float *__restrict__ rstd,
+                                                                    const T *__restrict__ d_xn, int64_t n_rows,
+                                                                    int d_model, int rows_per_block,
+                                                                    float *__restrict__ part) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= d_model) return;
+  const int64_t r0 = static_cast<int64_t>(blockIdx.y) * rows_per_block;
+  const int64_t r1 = r0 + rows_per_block < n_rows ? r0 + rows_per_block : n_rows;
+  float acc = 0.0f;
+  for (int64_t n = r0; n < r1; ++n)
+    acc = fmaf(to_f32(d_xn[n * d_model + c]) * to_f32(x[n * d_model + c]), rstd[n], acc);
+  part[static_cast<int64_t>(blockIdx.y) * d_model + c] = acc;
+}
+
+// out[c] = sum over parts, in part order
+__global__ __launch_bounds__(256) void colsum_kernel(const float *__restrict__ part, int n_parts, int n_cols,
+                                                     float *__restrict__ out) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= n_cols) return;
+  float acc = 0.0f;
+  for (int p = 0; p < n_parts; ++p) acc += part[static_cast<int64_t>(p) * n_cols + c];
+  out[c] = acc;
+}
+}  // namespace
+
+int rmsnorm_wgrad_parts(int64_t n_rows) {
+  const int64_t parts = (n_rows + 63) / 64;
+  return static_cast<int>(parts < 512 ? (parts < 1 ? 1 : parts) : 512);
+}
+
+hipError_t launch_rmsnorm_forward(int dtype, const void *x, const float *norm_w, float eps, int64_t n_rows, int d_model,
+                                  void *xn, float *rstd, hipStream_t s) {
+  if (d_model % 4 != 0) return hipErrorInvalidValue;
+  const dim3 grid(static_cast<unsigned>(ceil_div(n_rows, 4)));
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL((rmsnorm_fwd_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(x), norm_w, eps,
+                       n_rows, d_model, static_cast<bf16_t *>(xn), rstd);
+  else
+    hipLaunchKernelGGL((rmsnorm_fwd_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(x), norm_w, eps,
+                       n_rows, d_model, static_cast<float *>(xn), rstd);
+  return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_backward(int dtype, const void *x, const float *norm_w, const float *rstd, const void *d_xn,
+                                   const void *d_skip, int64_t n_rows, int d_model, void *d_x, float *part,
+                                   float *d_norm_w, hipStream_t s) {
+  if (d_model % 4 != 0) return hipErrorInvalidValue;
+  const dim3 grid(static_cast<unsigned>(ceil_div(n_rows, 4)));
+  const int parts = rmsnorm_wgrad_parts(n_rows);
+  const int rows_per_block = static_cast<int>(ceil_div(n_rows, parts));
+  const dim3 grid_w(static_cast<unsigned>(ceil_div(d_model, 256)), static_cast<unsigned>(parts));
+  if (dtype == ROM_DTYPE_BF16) {
+    hipLaunchKernelGGL((rmsnorm_bwd_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(x), norm_w, rstd,
+                       static_cast<const bf16_t *>(d_xn), static_cast<const bf16_t *>(d_skip), n_rows, d_model,
+                       static_cast<bf16_t *>(d_x));
+    hipLaunchKernelGGL((rmsnorm_wgrad_partial_kernel<bf16_t>), grid_w, dim3(256), 0, s, static_cast<const bf16_t *>(x),
+                       rstd, static_cast<const bf16_t *>(d_xn), n_rows, d_model, rows_per_block, part);
+  } else {
+    hipLaunchKernelGGL((rmsnorm_bwd_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(x), norm_w, rstd,
+                       static_cast<const float *>(d_xn), static_cast<const float *>(d_skip), n_rows, d_model,
+                       static_cast<float *>(d_x));
+    hipLaunchKernelGGL((rmsnorm_wgrad_partial_kernel<float>), grid_w, dim3(256), 0, s, static_cast<const float *>(x),
+                       rstd, static_cast<const float *>(d_xn), n_rows, d_model, rows_per_block, part);
+  }
+  hipLaunchKernelGGL(colsum_kernel, dim3(static_cast<unsigned>(ceil_div(d_model, 256))), dim3(256), 0, s, part, parts,
+                     d_model, d_norm_w);
+  return hipGetLastError();
+}
+
 hipError_t launch_wgrad(int dtype, const void *A, int64_t lda, int M, const void *Bm, int64_t ldb, int N,
                         const int32_t *rows_a, const int32_t *rows_b, const float *row_scale, const int32_t *offsets,
                         int n_groups, int64_t n_pos, float *C, hipStream_t s) {

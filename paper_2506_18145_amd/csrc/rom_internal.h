@@ -159,6 +159,15 @@ hipError_t launch_transpose(int dtype, const void *src, void *dst, int n_mats, i
 hipError_t launch_pack_dxdbl(int dtype, const float *d_dt_low, const float *d_bc, int64_t n_tok, int dt_rank,
                              void *d_xdbl, hipStream_t s);
 // dst[r, :] = scale[scale_idx ? scale_idx[r] : r] * src[src_idx ? src_idx[r] : r, :]
+// RMS norm of the pre-norm block: xn = x / sqrt(mean(x^2) + eps) * norm_w (type T), rstd f32 [n_rows]
+hipError_t launch_rmsnorm_forward(int dtype, const void *x, const float *norm_w, float eps, int64_t n_rows, int d_model,
+                                  void *xn, float *rstd, hipStream_t s);
+// its adjoint plus the skip: d_x = d_skip + d(RMSNorm)^T d_xn; d_norm_w = column sums of d_xn x rstd
+// (part: f32 [rmsnorm_wgrad_parts(n_rows), d_model], summed in part order)
+int rmsnorm_wgrad_parts(int64_t n_rows);
+hipError_t launch_rmsnorm_backward(int dtype, const void *x, const float *norm_w, const float *rstd, const void *d_xn,
+                                   const void *d_skip, int64_t n_rows, int d_model, void *d_x, float *part,
+                                   float *d_norm_w, hipStream_t s);
 hipError_t launch_scale_rows(int dtype, const void *src, const float *scale, const int32_t *src_idx,
                              const int32_t *scale_idx, int64_t n_rows, int n_cols, void *dst, hipStream_t s);
 // C[e][m][n] (f32) = sum over positions p in [offsets[e], offsets[e+1]) of scale[ra(p)] * A[ra(p)][m] * B[rb(p)][n]

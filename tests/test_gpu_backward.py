@@ -130,3 +130,55 @@ def test_backward_saved_matches_backward_bit_for_bit(kw):
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3"])
 def test_backward_full_size(name):
     run_backward(get_config(name))
+
+
+@pytest.mark.parametrize("kw,scale", [
+    (dict(cfg_id=170), 1.7),
+    (dict(cfg_id=171, dtype="fp32", seq_len=77), 0.6),
+    (dict(cfg_id=174, weight_std=0.1), 1.2),                      # a branch of the size of the skip term
+    (dict(cfg_id=172, top_k=2, gate_mode=1, d_model=264, d_inner=528, dt_rank=24, seq_len=130), 1.3),    # off the tile grids
+    (dict(cfg_id=173, batch=1, seq_len=5000, d_model=512, d_inner=1024, dt_rank=32), 1.4),                 # big-tile kernels
+])
+def test_block_backward(kw, scale):
+    """rom_block_backward (out = x + RoM(RMSNorm(x))) against the oracle's block backward: d_x, the norm
+    scale's gradient and every parameter gradient."""
+    cfg = small_cfg(**kw)
+    w, x = make_weights(cfg), make_input(cfg) * np.float32(scale)      # off unit RMS, so that 1/rms matters
+    x = round_to_bf16(x) if cfg.dtype == "bf16" else x
+    if w["b_router"] is None:
+        w["b_router"] = np.zeros(cfg.n_experts, np.float32)
+    rng = np.random.default_rng(cfg.cfg_id)
+    w["norm_w"] = (1.0 + 0.3 * rng.standard_normal(cfg.d_model)).astype(np.float32)
+    d_out = _d_out(cfg, x.shape)
+    layer = RomLayer(cfg, w)
+    xd, dd = layer.to_device(x), layer.to_device(d_out)
+    d_x, grads = layer.block_backward(xd, dd, eps=1e-5)
+    d_x2, grads2 = layer.block_backward(xd, dd, eps=1e-5)
+    torch.cuda.synchronize()
+    assert torch.equal(d_x, d_x2) and all(torch.equal(grads[k], grads2[k]) for k in grads), "not deterministic"
+    # the expert choice of the call's own forward pass (on the normalised input), left in its workspace
+    B, L = cfg.batch, cfg.seq_len
+    ws_keep = layer._ws
+    layer._ws = layer._blk_bwd_ws
+    gpu = {k: to_np(layer.ws_view(k, B, L)) for k in ("expert_idx", "gate", "counts", "offsets", "perm", "inv_perm", "logits")}
+    layer._ws = ws_keep
+    # the materialised norm against the oracle's, then the routing on exactly what the router saw
+    xn = to_np(layer.block_backward_xn(B, L))
+    assert rel_err(xn, O.rms_norm(x, w["norm_w"], 1e-5)) <= (2.0 ** -8 if cfg.dtype == "bf16" else 1e-6)
+    idx, n_excl = check_routing(cfg, gpu, xn, w)
+    ref = O.rom_block_backward(x, w, cfg.top_k, cfg.gate_mode, d_out, 1e-5, expert_idx=idx)
+    tol = TOL[cfg.dtype]
+    errs = {"d_x": rel_err(to_np(d_x), ref["d_x"]), "d_norm_w": rel_err(to_np(grads["d_norm_w"]), ref["d_norm_w"])}
+    # the norm's part of d_x alone: the skip term must not hide it
+    got_branch = to_np(d_x).astype(np.float64) - np.asarray(d_out, np.float64)
+    want_branch = ref["d_x"] - np.asarray(d_out, np.float64)
+    ulp = 2.0 ** -8 if cfg.dtype == "bf16" else 2.0 ** -24
+    slack = ulp * np.max(np.abs(ref["d_x"])) / np.max(np.abs(want_branch))
+    errs["d_x-d_out"] = max(rel_err(got_branch, want_branch) - slack, 0.0)
+    for name in PARAMS:
+        errs["d_" + name] = rel_err(to_np(grads["d_" + name]), ref["d_" + name])
+    ratio = float(np.max(np.abs(want_branch)) / np.max(np.abs(d_out)))
+    print(f"[block {cfg.name}] excluded={n_excl} branch/skip={ratio:.2f} " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()),
+          flush=True)
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, f"beyond tolerance {tol}: {bad}"
