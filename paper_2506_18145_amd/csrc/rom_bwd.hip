@@ -661,59 +661,130 @@ __global__ __launch_bounds__(256) void dx_finish_kernel(const T *__restrict__ dx
 // Per-run partial sums of d_w[i, j] = sum_t d_c_t x_{t-3+j} and d_b = sum_t d_c_t go to
 // partial[run][5][channel] and are added in run order by conv_bwd_finish_kernel.
 constexpr int kConvBwdRun = 128;
-template <typename T>
+constexpr int kConvBwdAhead = 8;     // steps whose rows are requested together
+// two consecutive channels of a row (4- or 8-byte accesses; the launcher checks evenness and alignment)
+__device__ __forceinline__ void conv_ld2(const bf16_t *p, float (&f)[2]) {
+  const unsigned u = *reinterpret_cast<const unsigned *>(p);
+  f[0] = bf16_to_f32(static_cast<bf16_t>(u & 0xffffu));
+  f[1] = bf16_to_f32(static_cast<bf16_t>(u >> 16));
+}
+__device__ __forceinline__ void conv_ld2(const float *p, float (&f)[2]) {
+  const float2 v = *reinterpret_cast<const float2 *>(p);
+  f[0] = v.x; f[1] = v.y;
+}
+__device__ __forceinline__ void conv_st2(bf16_t *p, const float (&f)[2]) {
+  *reinterpret_cast<unsigned *>(p) = static_cast<unsigned>(f32_to_bf16(f[0])) | (static_cast<unsigned>(f32_to_bf16(f[1])) << 16);
+}
+__device__ __forceinline__ void conv_st2(float *p, const float (&f)[2]) { *reinterpret_cast<float2 *>(p) = make_float2(f[0], f[1]); }
+
+// V = 2: a thread owns two neighbouring channels (half the memory instructions, twice their width)
+template <typename T, int V>
 __global__ __launch_bounds__(256) void conv_bwd_kernel(const T *__restrict__ xz, int64_t ld_xz,
                                                        const float *__restrict__ conv_w,
                                                        const float *__restrict__ conv_b, const T *__restrict__ du_a,
                                                        const T *__restrict__ du_b, int64_t L, int d_inner,
                                                        T *__restrict__ d_xpre, int64_t ld_dx,
                                                        float *__restrict__ partial) {
-  const int ch = blockIdx.x * blockDim.x + threadIdx.x;
+  static_assert(V == 1 || V == 2, "one or two channels per thread");
+  const int ch = (blockIdx.x * blockDim.x + threadIdx.x) * V;
   if (ch >= d_inner) return;
   const int64_t b = blockIdx.z, run = blockIdx.y;
   const int64_t t0 = run * kConvBwdRun;
   const int64_t t1 = t0 + kConvBwdRun < L ? t0 + kConvBwdRun : L;
-  const float4 wv = *reinterpret_cast<const float4 *>(conv_w + static_cast<int64_t>(ch) * 4);
-  const float w[4] = {wv.x, wv.y, wv.z, wv.w};
-  const float bias = conv_b ? conv_b[ch] : 0.0f;
+  float w[V][4], bias[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    const float4 wv = *reinterpret_cast<const float4 *>(conv_w + static_cast<int64_t>(ch + v) * 4);
+    w[v][0] = wv.x; w[v][1] = wv.y; w[v][2] = wv.z; w[v][3] = wv.w;
+    bias[v] = conv_b ? conv_b[ch + v] : 0.0f;
+  }
   const T *xr = xz + b * L * ld_xz + ch;
   const int64_t tok0 = b * L;
-  auto xin = [&](int64_t t) { return (t >= 0 && t < L) ? to_f32(xr[t * ld_xz]) : 0.0f; };
-  // d loss / d c_t (0 outside the sequence) from the four inputs x_{t-3..t} of c_t
-  auto dc_of = [&](int64_t t, float x0, float x1, float x2, float x3) {
-    if (t < 0 || t >= L) return 0.0f;
-    const float c = bias + w[0] * x0 + w[1] * x1 + w[2] * x2 + w[3] * x3;
-    const float sig = sigmoid_f32(c);
-    const float du = to_f32(du_a[(tok0 + t) * d_inner + ch]) + to_f32(du_b[(tok0 + t) * d_inner + ch]);
-    return du * sig * (1.0f + c * (1.0f - sig));
+  auto load = [&](const T *p, float (&f)[V]) __attribute__((always_inline)) {
+    if constexpr (V == 2) conv_ld2(p, f); else f[0] = to_f32(*p);
   };
-  float acc_w[4] = {0.f, 0.f, 0.f, 0.f}, acc_b = 0.0f;
+  // the rows a step needs from memory: x_{t+3} and the two d u rows of step t+3 (zeros outside the sequence)
+  auto fetch = [&](int64_t t, float (&x)[V], float (&ua)[V], float (&ub)[V]) __attribute__((always_inline)) {
+    if (t >= 0 && t < L) {
+      load(xr + t * ld_xz, x);
+      load(du_a + (tok0 + t) * d_inner + ch, ua);
+      load(du_b + (tok0 + t) * d_inner + ch, ub);
+    } else {
+#pragma unroll
+      for (int v = 0; v < V; ++v) x[v] = ua[v] = ub[v] = 0.0f;
+    }
+  };
+  // d loss / d c_t from the four inputs x_{t-3..t} of c_t and d u_t (d u = 0 outside the sequence gives 0)
+  auto dc_of = [&](const float (&x0)[V], const float (&x1)[V], const float (&x2)[V], const float (&x3)[V],
+                   const float (&ua)[V], const float (&ub)[V], float (&d)[V]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      const float c = bias[v] + w[v][0] * x0[v] + w[v][1] * x1[v] + w[v][2] * x2[v] + w[v][3] * x3[v];
+      const float sig = sigmoid_f32(c);
+      d[v] = (ua[v] + ub[v]) * sig * (1.0f + c * (1.0f - sig));
+    }
+  };
+  float acc_w[V][4], acc_b[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    acc_b[v] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc_w[v][j] = 0.0f;
+  }
   // the inputs x_{t-3} .. x_{t+3} and d_c of t .. t+3 slide along the run: one new x row, one new pair
-  // of d u rows and one output row per step
-  float xs[7];
+  // of d u rows and one output row per step.  The rows of kConvBwdAhead steps are requested together
+  // before any of them is used: a thread's loop is otherwise one memory round trip per step.
+  float xs[7][V], d0[V], d1[V], d2[V], d3[V];
+  {
+    float ua[3][V], ub[3][V], unused_a[V], unused_b[V];
 #pragma unroll
-  for (int k = 0; k < 6; ++k) xs[k] = xin(t0 - 3 + k);
-  float d0 = dc_of(t0, xs[0], xs[1], xs[2], xs[3]), d1 = dc_of(t0 + 1, xs[1], xs[2], xs[3], xs[4]),
-        d2 = dc_of(t0 + 2, xs[2], xs[3], xs[4], xs[5]);
-  for (int64_t t = t0; t < t1; ++t) {
-    xs[6] = xin(t + 3);
-    const float d3 = dc_of(t + 3, xs[3], xs[4], xs[5], xs[6]);
-    // x_t feeds c_t (tap 3), c_{t+1} (tap 2), c_{t+2} (tap 1), c_{t+3} (tap 0)
-    d_xpre[(tok0 + t) * ld_dx + ch] = from_f32<T>(w[3] * d0 + w[2] * d1 + w[1] * d2 + w[0] * d3);
-    acc_b += d0;
-    acc_w[0] = fmaf(d0, xs[0], acc_w[0]);
-    acc_w[1] = fmaf(d0, xs[1], acc_w[1]);
-    acc_w[2] = fmaf(d0, xs[2], acc_w[2]);
-    acc_w[3] = fmaf(d0, xs[3], acc_w[3]);
-    d0 = d1; d1 = d2; d2 = d3;
+    for (int k = 0; k < 3; ++k) fetch(t0 - 3 + k, xs[k], unused_a, unused_b);
 #pragma unroll
-    for (int k = 0; k < 6; ++k) xs[k] = xs[k + 1];
+    for (int k = 0; k < 3; ++k) fetch(t0 + k, xs[3 + k], ua[k], ub[k]);
+    dc_of(xs[0], xs[1], xs[2], xs[3], ua[0], ub[0], d0);
+    dc_of(xs[1], xs[2], xs[3], xs[4], ua[1], ub[1], d1);
+    dc_of(xs[2], xs[3], xs[4], xs[5], ua[2], ub[2], d2);
+  }
+  for (int64_t tb = t0; tb < t1; tb += kConvBwdAhead) {
+    float xn[kConvBwdAhead][V], una[kConvBwdAhead][V], unb[kConvBwdAhead][V];
+#pragma unroll
+    for (int k = 0; k < kConvBwdAhead; ++k) fetch(tb + 3 + k, xn[k], una[k], unb[k]);
+#pragma unroll
+    for (int k = 0; k < kConvBwdAhead; ++k) {
+      const int64_t t = tb + k;
+      if (t < t1) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) xs[6][v] = xn[k][v];
+        dc_of(xs[3], xs[4], xs[5], xs[6], una[k], unb[k], d3);
+        // x_t feeds c_t (tap 3), c_{t+1} (tap 2), c_{t+2} (tap 1), c_{t+3} (tap 0)
+        float o[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          o[v] = w[v][3] * d0[v] + w[v][2] * d1[v] + w[v][1] * d2[v] + w[v][0] * d3[v];
+          acc_b[v] += d0[v];
+          acc_w[v][0] = fmaf(d0[v], xs[0][v], acc_w[v][0]);
+          acc_w[v][1] = fmaf(d0[v], xs[1][v], acc_w[v][1]);
+          acc_w[v][2] = fmaf(d0[v], xs[2][v], acc_w[v][2]);
+          acc_w[v][3] = fmaf(d0[v], xs[3][v], acc_w[v][3]);
+          d0[v] = d1[v]; d1[v] = d2[v]; d2[v] = d3[v];
+        }
+        if constexpr (V == 2) conv_st2(d_xpre + (tok0 + t) * ld_dx + ch, o);
+        else d_xpre[(tok0 + t) * ld_dx + ch] = from_f32<T>(o[0]);
+#pragma unroll
+        for (int j = 0; j < 6; ++j)
+#pragma unroll
+          for (int v = 0; v < V; ++v) xs[j][v] = xs[j + 1][v];
+      }
+    }
   }
   const int64_t n_runs = gridDim.y;
-  float *dst = partial + ((b * n_runs + run) * 5) * d_inner + ch;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) dst[j * d_inner] = acc_w[j];
-  dst[4 * d_inner] = acc_b;
+  for (int v = 0; v < V; ++v) {
+    float *dst = partial + ((b * n_runs + run) * 5) * d_inner + ch + v;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dst[j * d_inner] = acc_w[v][j];
+    dst[4 * d_inner] = acc_b[v];
+  }
 }
 
 __global__ __launch_bounds__(256) void conv_bwd_finish_kernel(const float *__restrict__ partial, int64_t n_parts,
@@ -1429,15 +1500,21 @@ hipError_t launch_conv_backward(int dtype, const void *xz, int64_t ld_xz, const 
                                 const void *du_a, const void *du_b, int64_t B, int64_t L, int d_inner, void *d_xpre,
                                 int64_t ld_dx, float *partial, float *d_conv_w, float *d_conv_b, hipStream_t s) {
   const int64_t n_runs = ceil_div(L, kConvBwdRun);
-  const dim3 grid(static_cast<unsigned>(ceil_div(d_inner, 256)), static_cast<unsigned>(n_runs), static_cast<unsigned>(B));
-  if (dtype == ROM_DTYPE_BF16)
-    hipLaunchKernelGGL((conv_bwd_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(xz), ld_xz, conv_w,
-                       conv_b, static_cast<const bf16_t *>(du_a), static_cast<const bf16_t *>(du_b), L, d_inner,
-                       static_cast<bf16_t *>(d_xpre), ld_dx, partial);
-  else
-    hipLaunchKernelGGL((conv_bwd_kernel<float>), grid, dim3(256), 0, s, static_cast<const float *>(xz), ld_xz, conv_w,
-                       conv_b, static_cast<const float *>(du_a), static_cast<const float *>(du_b), L, d_inner,
-                       static_cast<float *>(d_xpre), ld_dx, partial);
+  const size_t eb = dtype == ROM_DTYPE_BF16 ? 2 : 4;
+  const auto al = [&](const void *p) { return reinterpret_cast<uintptr_t>(p) % (2 * eb) == 0; };
+  const bool two = d_inner % 2 == 0 && ld_xz % 2 == 0 && ld_dx % 2 == 0 && al(xz) && al(du_a) && al(du_b) && al(d_xpre);
+  const dim3 grid(static_cast<unsigned>(ceil_div(d_inner, two ? 512 : 256)), static_cast<unsigned>(n_runs),
+                  static_cast<unsigned>(B));
+#define ROM_CONV_BWD(T, V)                                                                                          \
+  hipLaunchKernelGGL((conv_bwd_kernel<T, V>), grid, dim3(256), 0, s, static_cast<const T *>(xz), ld_xz, conv_w, conv_b, \
+                     static_cast<const T *>(du_a), static_cast<const T *>(du_b), L, d_inner, static_cast<T *>(d_xpre),  \
+                     ld_dx, partial)
+  if (dtype == ROM_DTYPE_BF16) {
+    if (two) ROM_CONV_BWD(bf16_t, 2); else ROM_CONV_BWD(bf16_t, 1);
+  } else {
+    if (two) ROM_CONV_BWD(float, 2); else ROM_CONV_BWD(float, 1);
+  }
+#undef ROM_CONV_BWD
   hipLaunchKernelGGL(conv_bwd_finish_kernel, grid1d(5 * d_inner, 256), dim3(256), 0, s, partial, B * n_runs, d_inner,
                      d_conv_w, d_conv_b);
   return hipGetLastError();
