@@ -255,8 +255,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void scan_bwd_carry_kernel(
     const T *__restrict__ u, const T *__restrict__ dt, const float *__restrict__ bc, const T *__restrict__ z,
     int64_t ld_z, const T *__restrict__ dg, const float *__restrict__ gate, const float *__restrict__ A_log, int64_t L,
-    int d_inner, int n_chunks, int64_t chunk_len, float *__restrict__ carry_p, float *__restrict__ carry_q,
-    float *__restrict__ carry_r) {
+    int d_inner, int n_chunks, int64_t chunk_len, int fine_per_main, int n_main, float *__restrict__ carry_p,
+    float *__restrict__ carry_q, float *__restrict__ carry_r) {
   __shared__ BwdCarrySmem sm;
   const int tid = threadIdx.x;
   const int n = tid & 15, cl = tid >> 4;
@@ -272,34 +272,55 @@ __global__ __launch_bounds__(256) void scan_bwd_carry_kernel(
   const float *bc_b = bc + b * L * 32;
   const float *gate_b = gate ? gate + b * L : nullptr;
 
+  // The main kernel folds end states of the fine chunks that lie before its own chunk and start
+  // adjoints of those that lie after it: a fine chunk of the last main chunk needs no end state, one of
+  // the first main chunk no start adjoint (with two main chunks every block runs one pass, not two).
+  // The decay product is needed either way and comes from whichever pass runs.
+  const int64_t main_idx = k / fine_per_main;
+  const bool need_fwd = main_idx + 1 < n_main, need_bwd = main_idx >= 1;
   BwdTileRegs regs;
   float h = 0.0f, sum_dt = 0.0f;
-  bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts, te, d_inner, tid, false);
-  for (int64_t ti = 0; ti < n_tiles; ++ti) {
-    lds_barrier();
-    bwd_park_tile<BwdCarrySmem, false>(sm, regs, tid, false);
-    lds_barrier();
-    if (ti + 1 < n_tiles)
-      bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + (ti + 1) * kBwdTile, te, d_inner, tid, false);
-    else
-      bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + ti * kBwdTile, te, d_inner, tid, true);
+  if (need_fwd) {
+    bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts, te, d_inner, tid, false);
+    for (int64_t ti = 0; ti < n_tiles; ++ti) {
+      lds_barrier();
+      bwd_park_tile<BwdCarrySmem, false>(sm, regs, tid, false);
+      lds_barrier();
+      if (ti + 1 < n_tiles)
+        bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + (ti + 1) * kBwdTile, te, d_inner, tid, false);
+      else
+        bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + ti * kBwdTile, te, d_inner, tid, true);
 #pragma unroll 16
-    for (int s2 = 0; s2 < kBwdTile; ++s2) {
-      const float dts = sm.dt[s2][cl];
-      sum_dt += dts;
-      h = fmaf(fast_exp2(dts * a2), h, sm.u[s2][cl] * sm.bc[s2][n]);      // (u slot: dt * u)
+      for (int s2 = 0; s2 < kBwdTile; ++s2) {
+        const float dts = sm.dt[s2][cl];
+        sum_dt += dts;
+        h = fmaf(fast_exp2(dts * a2), h, sm.u[s2][cl] * sm.bc[s2][n]);      // (u slot: dt * u)
+      }
     }
+  } else {
+    bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + (n_tiles - 1) * kBwdTile, te, d_inner, tid, true);
   }
   float gq = 0.0f;
-  for (int64_t ti = n_tiles - 1; ti >= 0; --ti) {
-    lds_barrier();
-    bwd_park_tile<BwdCarrySmem, false>(sm, regs, tid, true);
-    lds_barrier();
-    if (ti > 0)
-      bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + (ti - 1) * kBwdTile, te, d_inner, tid, true);
+  if (need_bwd || !need_fwd) {                  // (a lone main chunk never launches this kernel; kept total)
+    for (int64_t ti = n_tiles - 1; ti >= 0; --ti) {
+      lds_barrier();
+      bwd_park_tile<BwdCarrySmem, false>(sm, regs, tid, true);
+      lds_barrier();
+      if (ti > 0)
+        bwd_fetch_tile<T>(regs, u_b, dt_b, z_b, ld_z, dg_b, bc_b, gate_b, ts + (ti - 1) * kBwdTile, te, d_inner, tid, true);
+      if (need_fwd) {
 #pragma unroll 16
-    for (int s2 = kBwdTile - 1; s2 >= 0; --s2)
-      gq = fmaf(sm.bc[s2][16 + n], sm.dy[s2][cl], gq) * fast_exp2(sm.dt[s2][cl] * a2);
+        for (int s2 = kBwdTile - 1; s2 >= 0; --s2)
+          gq = fmaf(sm.bc[s2][16 + n], sm.dy[s2][cl], gq) * fast_exp2(sm.dt[s2][cl] * a2);
+      } else {
+#pragma unroll 16
+        for (int s2 = kBwdTile - 1; s2 >= 0; --s2) {
+          const float dts = sm.dt[s2][cl];
+          sum_dt += dts;
+          gq = fmaf(sm.bc[s2][16 + n], sm.dy[s2][cl], gq) * fast_exp2(dts * a2);
+        }
+      }
+    }
   }
   const int64_t unit = (static_cast<int64_t>(blockIdx.y)) * gridDim.x + blockIdx.x;
   carry_p[unit * 256 + tid] = fast_exp2(sum_dt * a2);
@@ -1409,7 +1430,8 @@ static hipError_t launch_scan_backward_t(const void *u, const void *dt, const fl
     const dim3 fine_grid(static_cast<unsigned>(l.n_cb), static_cast<unsigned>(B * l.n_fine));
     hipLaunchKernelGGL((scan_bwd_carry_kernel<T>), fine_grid, dim3(256), 0, s, static_cast<const T *>(u),
                        static_cast<const T *>(dt), bc, static_cast<const T *>(z), ld_z, static_cast<const T *>(dg), gate,
-                       A_log, L, d_inner, l.n_fine, l.fine_len, ws + l.carry_p, ws + l.carry_q, ws + l.carry_r);
+                       A_log, L, d_inner, l.n_fine, l.fine_len, static_cast<int>(l.chunk_len / l.fine_len), l.n_chunks,
+                       ws + l.carry_p, ws + l.carry_q, ws + l.carry_r);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
