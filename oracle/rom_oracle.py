@@ -587,3 +587,46 @@ def rom_block_backward(x, w, top_k, gate_mode, d_out, eps=1e-5, expert_idx=None)
     res["d_x"] = np.asarray(d_out, F64) + d_x_norm
     res["d_norm_w"] = d_norm_w
     return res
+
+
+def ffn_moe_backward(x, w_gate_up, w_down, idx, gate, d_out, norm_w=None, eps=1e-5, skip=False):
+    """Gradients of ffn_moe_forward for d loss / d y = d_out [N, D_m], slot by slot:
+        h = W_gu,i x~,  a = SiLU(h_gate) * h_up,  o = W_down,i a,  y += gate * o
+    Returns d_x [N, D_m], d_w_gate_up [E, 2 D_f, D_m] (plain row order), d_w_down [E, D_m, D_f],
+    d_gate [N, K] (to be added to the gate gradient of the RoM layer that made the routing decision)
+    and, with a pre-norm, d_norm_w [D_m]."""
+    x = np.asarray(x, F64)
+    d_out = np.asarray(d_out, F64)
+    xin = x if norm_w is None else rms_norm(x, norm_w, eps)
+    idx = np.asarray(idx)
+    gate = np.asarray(gate, F64)
+    w_gate_up = np.asarray(w_gate_up, F64)
+    w_down = np.asarray(w_down, F64)
+    n_exp, d_f = w_gate_up.shape[0], w_gate_up.shape[1] // 2
+    d_xin = np.zeros_like(x)
+    d_wgu = np.zeros_like(w_gate_up)
+    d_wd = np.zeros_like(w_down)
+    d_gate = np.zeros_like(gate)
+    for k in range(idx.shape[1]):
+        for i in range(n_exp):
+            rows = np.nonzero(idx[:, k] == i)[0]
+            if not rows.size:
+                continue
+            h = xin[rows] @ w_gate_up[i].T
+            hg, hu = h[:, :d_f], h[:, d_f:]
+            sig = 1.0 / (1.0 + np.exp(-hg))
+            a = hg * sig * hu
+            d_gate[rows, k] = (d_out[rows] * (a @ w_down[i].T)).sum(axis=1)
+            d_o = gate[rows, k:k + 1] * d_out[rows]
+            d_wd[i] += d_o.T @ a
+            d_a = d_o @ w_down[i]
+            d_h = np.concatenate([d_a * hu * sig * (1.0 + hg * (1.0 - sig)), d_a * hg * sig], axis=1)
+            d_wgu[i] += d_h.T @ xin[rows]
+            d_xin[rows] += d_h @ w_gate_up[i]
+    res = {"d_w_gate_up": d_wgu, "d_w_down": d_wd, "d_gate": d_gate}
+    if norm_w is None:
+        d_x = d_xin
+    else:
+        d_x, res["d_norm_w"] = rms_norm_backward(x, norm_w, eps, d_xin)
+    res["d_x"] = d_x + d_out if skip else d_x
+    return res

@@ -840,6 +840,47 @@ def test_block_backward_matches_central_differences_of_the_block_forward():
     assert np.array_equal(res0["d_x"], d_out) and np.max(np.abs(res0["d_norm_w"])) == 0.0
 
 
+@pytest.mark.parametrize("pre_norm,skip,top_k", [(False, False, 1), (True, True, 2), (True, False, 3), (False, True, 2)])
+def test_ffn_moe_backward_against_library_differentiation(pre_norm, skip, top_k):
+    """The FFN-MoE layer of Eq. (14)/(15) written separately from torch routines (dense over the
+    experts, masked by the routing decision), differentiated by torch, against the oracle's
+    hand-written backward; the gate weights are an input here and get their own gradient."""
+    rng = np.random.default_rng(41 + top_k)
+    n_tok, d_m, d_f, n_exp = 23, 6, 5, 4
+    x = 1.3 * rng.standard_normal((n_tok, d_m))
+    wgu = 0.5 * rng.standard_normal((n_exp, 2 * d_f, d_m))
+    wd = 0.5 * rng.standard_normal((n_exp, d_m, d_f))
+    nw = 1.0 + 0.3 * rng.standard_normal(d_m) if pre_norm else None
+    idx = np.stack([rng.permutation(n_exp)[:top_k] for _ in range(n_tok)]).astype(np.int32)
+    gate = rng.uniform(0.1, 1.0, (n_tok, top_k))
+    d_out = rng.standard_normal((n_tok, d_m))
+    res = O.ffn_moe_backward(x, wgu, wd, idx, gate, d_out, nw, 1e-5, skip)
+
+    tx = torch.tensor(x, requires_grad=True)
+    tgu = torch.tensor(wgu, requires_grad=True)
+    tdn = torch.tensor(wd, requires_grad=True)
+    tg = torch.tensor(gate, requires_grad=True)
+    tn = torch.tensor(nw, requires_grad=True) if pre_norm else None
+    xin = F.rms_norm(tx, (d_m,), tn, 1e-5) if pre_norm else tx
+    weights = torch.zeros(n_tok, n_exp, dtype=torch.float64)
+    weights = weights.scatter_add(1, torch.as_tensor(idx, dtype=torch.int64), tg)      # R_i per expert (0 if not selected)
+    y = torch.zeros_like(tx)
+    for i in range(n_exp):
+        h = F.linear(xin, tgu[i])
+        y = y + weights[:, i:i + 1] * F.linear(F.silu(h[:, :d_f]) * h[:, d_f:], tdn[i])
+    if skip:
+        y = y + tx
+    assert np.allclose(y.detach().numpy(), O.ffn_moe_forward(x, wgu, wd, idx, gate, nw, 1e-5, skip), rtol=1e-11, atol=1e-13)
+    (y * torch.tensor(d_out)).sum().backward()
+    pairs = [("d_x", tx), ("d_w_gate_up", tgu), ("d_w_down", tdn), ("d_gate", tg)] + ([("d_norm_w", tn)] if pre_norm else [])
+    for name, t in pairs:
+        want = t.grad.numpy()
+        assert res[name].shape == want.shape, name
+        assert np.max(np.abs(want)) > 1e-6, name
+        assert np.max(np.abs(res[name] - want)) <= 1e-10 * (1.0 + np.max(np.abs(want))), name
+    assert pre_norm or "d_norm_w" not in res
+
+
 def test_scan_backward_closed_forms():
     """Constant coefficients: y_T depends on u_s through C . a^(T-s) . dt B (+ D at s = T), so a
     one-hot d_y at time T gives that as d_u; and the adjoint state after the last step back is
