@@ -203,9 +203,25 @@ def ffn_moe_rate(cfg, d_ff, steps, warmup):
     ms = e0.elapsed_time(e1) / steps
     n_tok = x.shape[0]
     flops = 6.0 * n_tok * cfg.top_k * Dm * d_ff
+    # backward of the same layer (forward recomputation with the pre-activations kept, then the adjoint)
+    d_out = torch.randn(x.shape, generator=g, device="cuda:0").to(t)
+    for _ in range(3):
+        ffn.backward(x, routing, d_out, pre_norm=True, add_skip=True)
+    e0.record()
+    n_bwd = max(3, steps // 4)
+    for _ in range(n_bwd):
+        d_x, _, _ = ffn.backward(x, routing, d_out, pre_norm=True, add_skip=True)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_bwd = e0.elapsed_time(e1) / n_bwd
     return {"workload": f"{cfg.name}'s tokens and routing, SwiGLU experts d_ff={d_ff}, pre-norm + skip",
             "ms_per_call": ms, "tokens_per_s": n_tok / (ms * 1e-3), "bound": "mfma",
-            "achieved_tflops": flops / (ms * 1e-3) / 1e12, "frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+            "achieved_tflops": flops / (ms * 1e-3) / 1e12, "frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "backward": {"workload": "rom_ffn_moe_backward: forward recomputation + gradients w.r.t. x, the gate weights, "
+                                     "the norm scale and both expert weights",
+                         "ms_per_call": ms_bwd, "tokens_per_s": n_tok / (ms_bwd * 1e-3),
+                         "gemm_tflops": 4.0 * flops / (ms_bwd * 1e-3) / 1e12,
+                         "gradients_finite": bool(torch.isfinite(d_x.float()).all().item())}}
 
 
 def hybrid_stack_rate(cfg, n_layers, d_ff, steps, warmup):

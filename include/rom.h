@@ -367,6 +367,29 @@ ROM_API int rom_ffn_moe_forward(const rom_dims *dims, int32_t d_ff, const rom_ff
                         const int32_t *offsets, const int32_t *perm, const int32_t *inv_perm,
                         const float *gate, void *out, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* Backward pass of the FFN-MoE layer: gradients of y = (x +) sum_k gate_k f_{e_k}(x~), x~ = RMSNorm(x) or x.
+ *   w             the packed weights of rom_ffn_pack_gate_up WITHOUT the norm's scale folded in
+ *   norm_weight   f32 [d_model] (device): the experts see RMSNorm(x); NULL: they see x
+ *   x, d_out      T [N, d_model];  offsets, perm, inv_perm, gate: the routing decision, as for the forward
+ *   d_x           T [N, d_model], written (aliases neither x nor d_out)
+ *   d_gate        f32 [N, K], written: d loss / d gate of every slot - the caller adds it to the gate
+ *                 gradient of the RoM layer whose router made the decision
+ *   grads         d_w_gate_up f32 [E, 2*d_ff, d_model] in the PACKED row order, d_w_down f32
+ *                 [E, d_model, d_ff], d_norm_weight f32 [d_model] (required iff norm_weight != NULL)
+ *   ws            rom_ffn_backward_workspace_bytes(dims, d_ff, N) bytes, 256-byte aligned
+ * The call recomputes the forward pass with the pre-activations kept.  Deterministic. */
+typedef struct rom_ffn_grads {
+  float *d_w_gate_up;
+  float *d_w_down;
+  float *d_norm_weight;
+} rom_ffn_grads;
+ROM_API size_t rom_ffn_backward_workspace_bytes(const rom_dims *dims, int32_t d_ff, int64_t N);
+ROM_API int rom_ffn_moe_backward(const rom_dims *dims, int32_t d_ff, const rom_ffn_weights *w,
+                                 const float *norm_weight, float eps, int add_skip, const void *x, int64_t N,
+                                 const int32_t *offsets, const int32_t *perm, const int32_t *inv_perm,
+                                 const float *gate, const void *d_out, void *d_x, float *d_gate,
+                                 const rom_ffn_grads *grads, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* The hybrid of the appendix (RoM + FFN-MoE with shared routing), as a stack: layer j is the RoM
  * block blocks[j]; if ffns[j].w_gate_up is not NULL an FFN-MoE block (pre-norm if ffn_pre_norm,
  * always with its skip) follows it and runs on the routing decision that RoM block has just made

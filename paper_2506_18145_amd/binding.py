@@ -45,6 +45,10 @@ class _RomFfnWeights(ctypes.Structure):
     _fields_ = [("w_gate_up", ctypes.c_void_p), ("w_down", ctypes.c_void_p)]
 
 
+class _RomFfnGrads(ctypes.Structure):
+    _fields_ = [("d_w_gate_up", ctypes.c_void_p), ("d_w_down", ctypes.c_void_p), ("d_norm_weight", ctypes.c_void_p)]
+
+
 class _RomWsLayout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in (
         "total_bytes", "expert_idx", "gate", "counts", "offsets", "perm", "inv_perm", "logits", "xz",
@@ -144,6 +148,11 @@ def load_library() -> ctypes.CDLL:
     lib.rom_ffn_moe_forward.restype = ctypes.c_int
     lib.rom_ffn_moe_forward.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, ctypes.POINTER(_RomFfnWeights),
                                         ctypes.c_int, F32, ctypes.c_int, P, I64, P, P, P, P, P, P, SZ, P]
+    lib.rom_ffn_backward_workspace_bytes.restype = SZ
+    lib.rom_ffn_backward_workspace_bytes.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, I64]
+    lib.rom_ffn_moe_backward.restype = ctypes.c_int
+    lib.rom_ffn_moe_backward.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, ctypes.POINTER(_RomFfnWeights), P, F32,
+                                         ctypes.c_int, P, I64, P, P, P, P, P, P, P, ctypes.POINTER(_RomFfnGrads), P, SZ, P]
     lib.rom_hybrid_stack_forward.restype = ctypes.c_int
     lib.rom_hybrid_stack_forward.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, ctypes.POINTER(_RomBlock),
                                              ctypes.POINTER(_RomFfnWeights), ctypes.c_int, ctypes.c_int, F32, P,
@@ -784,6 +793,7 @@ class RomFfnMoe:
         self.norm_w = conv(weights["norm_w"], torch.float32) if weights.get("norm_w") is not None else None
         self._packed: Dict[bool, torch.Tensor] = {}
         self._ws: Optional[torch.Tensor] = None
+        self._bwd_ws: Optional[torch.Tensor] = None
 
     def packed(self, pre_norm: bool, drop_plain: bool = False) -> torch.Tensor:
         """w_gate_up in the library's packed row order, with the pre-norm's scale folded in or not."""
@@ -811,6 +821,43 @@ class RomFfnMoe:
                             pre_norm, self.eps, add_skip, x, n, routing["offsets"], routing["perm"],
                             routing["inv_perm"], routing["gate"], out, self._ws)
         return out
+
+    def backward(self, x: torch.Tensor, routing, d_out: torch.Tensor, pre_norm: bool = False, add_skip: bool = False):
+        """(d_x, d_gate [N, K], {d_w_gate_up (packed row order), d_w_down, d_norm_w}) of forward(x, routing, ...)."""
+        n = x.numel() // self.dims.d_model
+        need = rom_ffn_backward_workspace_bytes(self.dims, self.d_ff, max(n, 1))
+        if need == 0:
+            raise RomError("rom_ffn_backward_workspace_bytes returned 0: unsupported dims or d_ff")
+        if self._bwd_ws is None or self._bwd_ws.numel() < need:
+            self._bwd_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        d_x = torch.empty_like(x)
+        f32 = dict(dtype=torch.float32, device=self.device)
+        d_gate = torch.empty((n, self.dims.top_k), **f32)
+        grads = {"d_w_gate_up": torch.empty(self.w_down.shape[0], 2 * self.d_ff, self.dims.d_model, **f32),
+                 "d_w_down": torch.empty(self.w_down.shape, **f32)}
+        if pre_norm:
+            grads["d_norm_w"] = torch.empty(self.dims.d_model, **f32)
+        rom_ffn_moe_backward(self.dims, self.d_ff, self.packed(False), self.w_down, self.norm_w if pre_norm else None,
+                             self.eps, add_skip, x, n, routing["offsets"], routing["perm"], routing["inv_perm"],
+                             routing["gate"], d_out, d_x, d_gate, grads["d_w_gate_up"], grads["d_w_down"],
+                             grads.get("d_norm_w"), self._bwd_ws)
+        return d_x, d_gate, grads
+
+
+def rom_ffn_backward_workspace_bytes(dims: RomDims, d_ff: int, N: int) -> int:
+    return int(load_library().rom_ffn_backward_workspace_bytes(ctypes.byref(dims), d_ff, N))
+
+
+def rom_ffn_moe_backward(dims, d_ff, w_gate_up_packed, w_down, norm_weight, eps, add_skip, x, N, offsets, perm, inv_perm,
+                         gate, d_out, d_x, d_gate, d_w_gate_up, d_w_down, d_norm_weight, ws):
+    """w_gate_up_packed: packed WITHOUT the norm's scale; norm_weight None: no pre-norm."""
+    wst = _RomFfnWeights(_ptr(w_gate_up_packed), _ptr(w_down))
+    gst = _RomFfnGrads(_ptr(d_w_gate_up), _ptr(d_w_down), _ptr(d_norm_weight))
+    code = load_library().rom_ffn_moe_backward(
+        ctypes.byref(dims), d_ff, ctypes.byref(wst), _ptr(norm_weight), eps, int(bool(add_skip)), _ptr(x), N, _ptr(offsets),
+        _ptr(perm), _ptr(inv_perm), _ptr(gate), _ptr(d_out), _ptr(d_x), _ptr(d_gate), ctypes.byref(gst), _ptr(ws),
+        _nbytes(ws), _stream())
+    _check(code, "rom_ffn_moe_backward")
 
 
 class RomHybridStack:

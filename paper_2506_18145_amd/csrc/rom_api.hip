@@ -906,6 +906,140 @@ int rom_ffn_moe_forward(const rom_dims *dims, int32_t d_ff, const rom_ffn_weight
   return ROM_OK;
 }
 
+namespace {
+// workspace of rom_ffn_moe_backward
+struct FfnBwdPlan {
+  size_t total, tok_of_pos, xn, rstd, h, a, o, dsc, d_a, d_h, wt_down, wt_gu, d_xin, part;
+};
+FfnBwdPlan make_ffn_bwd_plan(const rom_dims *d, int32_t d_ff, int64_t n_tok) {
+  FfnBwdPlan p;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off += (bytes + kAlign - 1) / kAlign * kAlign;
+    return at;
+  };
+  const size_t N = static_cast<size_t>(n_tok), S = N * d->top_k, b = d->dtype == ROM_DTYPE_BF16 ? 2 : 4;
+  const size_t Dm = d->d_model, Df = d_ff, E = d->n_experts;
+  p.tok_of_pos = take(S * 4);
+  p.xn = take(N * Dm * b);
+  p.rstd = take(N * 4);
+  p.h = take(S * 2 * Df * b);
+  p.a = take(S * Df * b);
+  p.o = take(S * Dm * b);            // the experts' outputs per position, later the input gradient per position
+  p.dsc = take(S * Dm * b);
+  p.d_a = take(S * Df * b);
+  p.d_h = take(S * 2 * Df * b);
+  p.wt_down = take(E * Df * Dm * b);     // transposed weights, written only where the GEMM cannot read W contraction-major
+  p.wt_gu = take(E * 2 * Df * Dm * b);
+  p.d_xin = take(N * Dm * b);
+  p.part = take(static_cast<size_t>(rmsnorm_wgrad_parts(n_tok)) * Dm * 4);
+  p.total = off;
+  return p;
+}
+}  // namespace
+
+size_t rom_ffn_backward_workspace_bytes(const rom_dims *dims, int32_t d_ff, int64_t N) {
+  if (check_ffn(dims, d_ff) != ROM_OK || N < 0) return 0;
+  return make_ffn_bwd_plan(dims, d_ff, N > 0 ? N : 1).total;
+}
+
+int rom_ffn_moe_backward(const rom_dims *dims, int32_t d_ff, const rom_ffn_weights *w, const float *norm_weight, float eps,
+                         int add_skip, const void *x, int64_t N, const int32_t *offsets, const int32_t *perm,
+                         const int32_t *inv_perm, const float *gate, const void *d_out, void *d_x, float *d_gate,
+                         const rom_ffn_grads *gr, void *ws, size_t ws_bytes, void *hip_stream) {
+  int rc = check_ffn(dims, d_ff);
+  if (rc != ROM_OK) return rc;
+  if (!w || !w->w_gate_up || !w->w_down || !aligned16(w->w_gate_up) || !aligned16(w->w_down)) return ROM_E_INVAL;
+  const bool pre_norm = norm_weight != nullptr;
+  if (N < 0 || (pre_norm && (!(eps >= 0.0f) || !aligned16(norm_weight)))) return ROM_E_INVAL;
+  if (N == 0) return ROM_OK;
+  if (!x || !d_out || !d_x || d_x == x || d_x == d_out || !offsets || !perm || !inv_perm || !gate || !d_gate || !gr || !ws)
+    return ROM_E_INVAL;
+  if (!gr->d_w_gate_up || !gr->d_w_down || !aligned16(gr->d_w_gate_up) || !aligned16(gr->d_w_down) ||
+      (pre_norm && !gr->d_norm_weight))
+    return ROM_E_INVAL;
+  if (!aligned16(x) || !aligned16(d_out) || !aligned16(d_x) || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0)
+    return ROM_E_INVAL;
+  if (N * dims->top_k > (1ll << 24) || dims->d_model % 8 != 0) return ROM_E_UNSUPPORTED;
+  const FfnBwdPlan p = make_ffn_bwd_plan(dims, d_ff, N);
+  if (ws_bytes < p.total) return ROM_E_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char *base = static_cast<char *>(ws);
+  auto at = [&](size_t off) { return base + off; };
+  const int K = dims->top_k, E = dims->n_experts, Dm = dims->d_model, dt = dims->dtype;
+  const int64_t S = N * K;
+  const bool f32 = dt == ROM_DTYPE_F32;
+  int32_t *tok_of_pos = reinterpret_cast<int32_t *>(at(p.tok_of_pos));
+  float *rstd = reinterpret_cast<float *>(at(p.rstd));
+  ROM_TRY(launch_ffn_prep(dt, perm, K, S, x, Dm, eps, tok_of_pos, nullptr, s));
+  const void *xin = x;
+  if (pre_norm) {       // the experts' input, materialised in the activation type
+    ROM_TRY(launch_rmsnorm_forward(dt, x, norm_weight, eps, N, Dm, at(p.xn), rstd, s));
+    xin = at(p.xn);
+  }
+  // plain grouped GEMM over the sorted positions; W_fwd != NULL: contract over W's row index instead
+  // (W_fwd [E][k_in][n_out] read as it is where the kernel can, else through its transpose in wt)
+  auto gemm = [&](const void *A, int64_t lda, const int32_t *a_rows, int64_t a_row_count, const void *W, int n_out, int k_in,
+                  void *C, const int32_t *c_rows, const void *W_fwd, void *wt) -> int {
+    GemmArgs ga;
+    memset(&ga, 0, sizeof(ga));
+    ga.dtype = dt;
+    ga.A = A; ga.lda = lda; ga.a_rows = a_rows; ga.a_span = a_row_count * lda;
+    ga.W = W; ga.N = n_out; ga.K = k_in;
+    ga.offsets = offsets; ga.n_groups = E; ga.M = S;
+    ga.C = C; ga.ldc = n_out; ga.c_rows = c_rows;
+    if (W_fwd) {
+      GemmArgs gk = ga;
+      gk.W = W_fwd; gk.w_kmajor = 1;
+      if (grouped_gemm_takes_kmajor(gk)) {
+        ga = gk;
+      } else {
+        ROM_TRY(launch_transpose(dt, W_fwd, wt, E, k_in, n_out, s));
+        ga.W = wt;
+      }
+    }
+    ROM_TRY(launch_grouped_gemm(ga, s));
+    return ROM_OK;
+  };
+#define ROM_RC(expr)               \
+  do {                             \
+    const int rc_ = (expr);        \
+    if (rc_ != ROM_OK) return rc_; \
+  } while (0)
+  // forward recomputation: h = W_gu x~ (pre-activations kept this time), a = SiLU(gate) * up, o = W_down a
+  ROM_RC(gemm(xin, Dm, tok_of_pos, N, w->w_gate_up, 2 * d_ff, Dm, at(p.h), nullptr, nullptr, nullptr));
+  ROM_TRY(launch_swiglu(dt, at(p.h), at(p.a), S, d_ff, s));
+  ROM_RC(gemm(at(p.a), d_ff, nullptr, S, w->w_down, Dm, d_ff, at(p.o), nullptr, nullptr, nullptr));
+  // d gate of a slot: d_out of its token against its expert's output
+  ROM_TRY(launch_gate_backward(dt, d_out, at(p.o), inv_perm, K, S, Dm, d_gate, s));
+  // gate-weighted d_out per position; d W_down = sum over an expert's positions of (gate d_out)^T a; d a
+  ROM_TRY(launch_scale_rows(dt, d_out, gate, tok_of_pos, perm, S, Dm, at(p.dsc), s));
+  ROM_TRY(launch_wgrad(dt, at(p.dsc), Dm, Dm, at(p.a), d_ff, d_ff, nullptr, nullptr, nullptr, offsets, E, S,
+                       gr->d_w_down, s));
+  ROM_RC(gemm(at(p.dsc), Dm, nullptr, S, nullptr, d_ff, Dm, at(p.d_a), nullptr, w->w_down, at(p.wt_down)));
+  // through the SwiGLU; d W_gu (packed row order) and the input gradient per position
+  ROM_TRY(launch_swiglu_backward(dt, at(p.h), at(p.d_a), at(p.d_h), S, d_ff, s));
+  ROM_TRY(launch_wgrad(dt, at(p.d_h), 2 * d_ff, 2 * d_ff, xin, Dm, Dm, nullptr, tok_of_pos, nullptr, offsets, E, S,
+                       gr->d_w_gate_up, s));
+  // input gradient: per position, then to token order (top-1: scattered by the GEMM; top-K: the K rows of a token added)
+  void *d_xin = (pre_norm || add_skip) ? static_cast<void *>(at(p.d_xin)) : d_x;
+  if (K == 1) {
+    ROM_RC(gemm(at(p.d_h), 2 * d_ff, nullptr, S, nullptr, Dm, 2 * d_ff, d_xin, tok_of_pos, w->w_gate_up, at(p.wt_gu)));
+  } else {
+    ROM_RC(gemm(at(p.d_h), 2 * d_ff, nullptr, S, nullptr, Dm, 2 * d_ff, at(p.o), nullptr, w->w_gate_up, at(p.wt_gu)));
+    ROM_TRY(launch_slot_sum(f32, f32, at(p.o), Dm, d_xin, Dm, inv_perm, N, K, Dm, nullptr, 0, nullptr, s));
+  }
+#undef ROM_RC
+  if (pre_norm) {
+    ROM_TRY(launch_rmsnorm_backward(dt, x, norm_weight, rstd, d_xin, add_skip ? d_out : nullptr, N, Dm, d_x,
+                                    reinterpret_cast<float *>(at(p.part)), gr->d_norm_weight, s));
+  } else if (add_skip) {
+    ROM_TRY(launch_add(dt, d_xin, d_out, d_x, N * Dm, s));
+  }
+  return ROM_OK;
+}
+
 int rom_hybrid_stack_forward(const rom_dims *dims, int32_t d_ff, const rom_block *blocks,
                              const rom_ffn_weights *ffns, int ffn_pre_norm, int n_layers, float eps,
                              const void *x, int64_t B, int64_t L, const float *conv_state_in,

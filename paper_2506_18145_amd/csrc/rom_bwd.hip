@@ -1612,7 +1612,7 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T *__restrict__ 
   }
 }
 
-// d_x = d_skip + r (d_xn norm_w - x^ mean_d(d_xn norm_w x^)),  x^ = x r
+// d_x = d_skip + r (d_xn norm_w - x^ mean_d(d_xn norm_w x^)),  x^ = x r   (d_skip may be NULL: no skip connection)
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T *__restrict__ x, const float *__restrict__ norm_w,
                                                           const float *__restrict__ rstd, const T *__restrict__ d_xn,
@@ -1641,7 +1641,8 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T *__restrict__ 
     float v[4], dv[4], sk[4], o[4];
     bwd_load4(xr + c, v);
     bwd_load4(dr + c, dv);
-    bwd_load4(d_skip + row * d_model + c, sk);
+    if (d_skip) bwd_load4(d_skip + row * d_model + c, sk);
+    else sk[0] = sk[1] = sk[2] = sk[3] = 0.0f;
     const float4 g = *reinterpret_cast<const float4 *>(norm_w + c);
     o[0] = sk[0] + r * (dv[0] * g.x - v[0] * r * m);
     o[1] = sk[1] + r * (dv[1] * g.y - v[1] * r * m);
@@ -1668,14 +1669,19 @@ __global__ __launch_bounds__(256) void rmsnorm_wgrad_partial_kernel(const T *__r
   part[static_cast<int64_t>(blockIdx.y) * d_model + c] = acc;
 }
 
-// out[c] = sum over parts, in part order
+// out[c] = sum over parts: a block owns 64 columns, its four waves each add every fourth part in part
+// order, then the four sums are added in wave order (a fixed order either way)
 __global__ __launch_bounds__(256) void colsum_kernel(const float *__restrict__ part, int n_parts, int n_cols,
                                                      float *__restrict__ out) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= n_cols) return;
+  __shared__ float sums[4][64];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
   float acc = 0.0f;
-  for (int p = 0; p < n_parts; ++p) acc += part[static_cast<int64_t>(p) * n_cols + c];
-  out[c] = acc;
+  if (c < n_cols)
+    for (int p = q; p < n_parts; p += 4) acc += part[static_cast<int64_t>(p) * n_cols + c];
+  sums[q][lane] = acc;
+  __syncthreads();
+  if (q == 0 && c < n_cols) out[c] = (sums[0][lane] + sums[1][lane]) + (sums[2][lane] + sums[3][lane]);
 }
 }  // namespace
 
@@ -1718,7 +1724,7 @@ hipError_t launch_rmsnorm_backward(int dtype, const void *x, const float *norm_w
     hipLaunchKernelGGL((rmsnorm_wgrad_partial_kernel<float>), grid_w, dim3(256), 0, s, static_cast<const float *>(x),
                        rstd, static_cast<const float *>(d_xn), n_rows, d_model, rows_per_block, part);
   }
-  hipLaunchKernelGGL(colsum_kernel, dim3(static_cast<unsigned>(ceil_div(d_model, 256))), dim3(256), 0, s, part, parts,
+  hipLaunchKernelGGL(colsum_kernel, dim3(static_cast<unsigned>(ceil_div(d_model, 64))), dim3(256), 0, s, part, parts,
                      d_model, d_norm_w);
   return hipGetLastError();
 }

@@ -162,7 +162,7 @@ hipError_t launch_pack_dxdbl(int dtype, const float *d_dt_low, const float *d_bc
 // RMS norm of the pre-norm block: xn = x / sqrt(mean(x^2) + eps) * norm_w (type T), rstd f32 [n_rows]
 hipError_t launch_rmsnorm_forward(int dtype, const void *x, const float *norm_w, float eps, int64_t n_rows, int d_model,
                                   void *xn, float *rstd, hipStream_t s);
-// its adjoint plus the skip: d_x = d_skip + d(RMSNorm)^T d_xn; d_norm_w = column sums of d_xn x rstd
+// its adjoint plus the skip: d_x = d_skip + d(RMSNorm)^T d_xn (d_skip NULL: none); d_norm_w = column sums of d_xn x rstd
 // (part: f32 [rmsnorm_wgrad_parts(n_rows), d_model], summed in part order)
 int rmsnorm_wgrad_parts(int64_t n_rows);
 hipError_t launch_rmsnorm_backward(int dtype, const void *x, const float *norm_w, const float *rstd, const void *d_xn,
@@ -216,6 +216,11 @@ hipError_t launch_probe_scan(int parts, int lds, int n_blocks, int tiles, float 
 // a[p, 8b + t] = SiLU(h[p, 16b + t]) * h[p, 16b + 8 + t], t < 8: h's columns are blocks of 8 gate + 8 up
 // features (h T [n_rows, 2*d_ff], a T [n_rows, d_ff]; d_ff % 8 == 0)
 hipError_t launch_swiglu(int dtype, const void *h, void *a, int64_t n_rows, int d_ff, hipStream_t s);
+// its adjoint: d_h (packed column order, T [n_rows, 2 d_ff]) from h and d_a (T [n_rows, d_ff])
+hipError_t launch_swiglu_backward(int dtype, const void *h, const void *d_a, void *d_h, int64_t n_rows, int d_ff,
+                                  hipStream_t s);
+// dst = a + b over n_elems elements of type T (a multiple of 16 bytes; 16-byte aligned)
+hipError_t launch_add(int dtype, const void *a, const void *b, void *dst, int64_t n_elems, hipStream_t s);
 // tok_of_pos[p] = perm[p] / K; rstd_sorted (may be NULL) [p] = 1 / sqrt(mean(x[tok_of_pos[p]]^2) + eps)
 hipError_t launch_ffn_prep(int dtype, const int32_t *perm, int top_k, int64_t n_slots, const void *x,
                            int d_model, float eps, int32_t *tok_of_pos, float *rstd_sorted, hipStream_t s);

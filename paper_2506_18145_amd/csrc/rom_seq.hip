@@ -891,6 +891,53 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const T *__restrict__ h, T 
   o.store(a + row * d_ff + c0);
 }
 
+// adjoint of the SwiGLU above, in the same packed column order:
+// d_h[p, 16b + t] = d_a[p, 8b + t] * up * s (1 + gate (1 - s)),  d_h[p, 16b + 8 + t] = d_a[p, 8b + t] * gate * s,  s = sigmoid(gate)
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T *__restrict__ h, const T *__restrict__ d_a,
+                                                         T *__restrict__ d_h, int64_t n_rows, int d_ff) {
+  constexpr int V = Chunk<T>::kElems;
+  const int groups = d_ff / V;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (idx >= n_rows * groups) return;
+  const int64_t row = idx / groups;
+  const int c0 = static_cast<int>(idx % groups) * V;
+  Chunk<T> g, u, da, og, ou;
+  const int goff = 16 * (c0 / 8) + (c0 % 8);
+  g.load(h + row * 2 * d_ff + goff);
+  u.load(h + row * 2 * d_ff + goff + 8);
+  da.load(d_a + row * d_ff + c0);
+  float dg[V], du[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) {
+    const float gv = g.get(i), sg = 1.0f / (1.0f + __expf(-gv));
+    dg[i] = da.get(i) * u.get(i) * sg * (1.0f + gv * (1.0f - sg));
+    du[i] = da.get(i) * gv * sg;
+  }
+#pragma unroll
+  for (int i = 0; i < V / 2; ++i) {
+    og.set_pair(i, dg[2 * i], dg[2 * i + 1]);
+    ou.set_pair(i, du[2 * i], du[2 * i + 1]);
+  }
+  og.store(d_h + row * 2 * d_ff + goff);
+  ou.store(d_h + row * 2 * d_ff + goff + 8);
+}
+
+// dst = a + b, 16 bytes per thread
+template <typename T>
+__global__ __launch_bounds__(256) void add_kernel(const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ dst,
+                                                  int64_t n_chunks) {
+  constexpr int V = Chunk<T>::kElems;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (idx >= n_chunks) return;
+  Chunk<T> x, y, o;
+  x.load(a + idx * V);
+  y.load(b + idx * V);
+#pragma unroll
+  for (int i = 0; i < V / 2; ++i) o.set_pair(i, x.get(2 * i) + y.get(2 * i), x.get(2 * i + 1) + y.get(2 * i + 1));
+  o.store(dst + idx * V);
+}
+
 // tok_of_pos[p] = perm[p] / K for the sorted positions of a routing decision made elsewhere
 __global__ __launch_bounds__(256) void tok_of_pos_kernel(const int32_t *__restrict__ perm, int top_k,
                                                          int64_t n_slots, int32_t *__restrict__ tok_of_pos) {
@@ -1035,6 +1082,32 @@ hipError_t launch_swiglu(int dtype, const void *h, void *a, int64_t n_rows, int 
   else
     hipLaunchKernelGGL(swiglu_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(h),
                        static_cast<float *>(a), n_rows, d_ff);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu_backward(int dtype, const void *h, const void *d_a, void *d_h, int64_t n_rows, int d_ff,
+                                  hipStream_t s) {
+  const int V = dtype == ROM_DTYPE_BF16 ? 8 : 4;
+  const dim3 grid = grid1d(n_rows * (d_ff / V), 256);
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL(swiglu_bwd_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(h),
+                       static_cast<const bf16_t *>(d_a), static_cast<bf16_t *>(d_h), n_rows, d_ff);
+  else
+    hipLaunchKernelGGL(swiglu_bwd_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(h),
+                       static_cast<const float *>(d_a), static_cast<float *>(d_h), n_rows, d_ff);
+  return hipGetLastError();
+}
+
+hipError_t launch_add(int dtype, const void *a, const void *b, void *dst, int64_t n_elems, hipStream_t s) {
+  const int V = dtype == ROM_DTYPE_BF16 ? 8 : 4;
+  if (n_elems % V != 0) return hipErrorInvalidValue;
+  const dim3 grid = grid1d(n_elems / V, 256);
+  if (dtype == ROM_DTYPE_BF16)
+    hipLaunchKernelGGL(add_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(a),
+                       static_cast<const bf16_t *>(b), static_cast<bf16_t *>(dst), n_elems / V);
+  else
+    hipLaunchKernelGGL(add_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(a),
+                       static_cast<const float *>(b), static_cast<float *>(dst), n_elems / V);
   return hipGetLastError();
 }
 

@@ -247,6 +247,33 @@ int main() {
     CHECK(rom_gdn_block_forward(&m, &gw, st, 1e-5f, addr, 0, 64, 1e-5f, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 4096, nullptr) == ROM_OK);
   }
 
+  // ---- FFN-MoE layer, forward and backward: validation before any launch
+  {
+    const rom_dims d = shapes[0];
+    rom_ffn_weights fw;
+    fw.w_gate_up = addr; fw.w_down = addr;
+    rom_ffn_grads fg;
+    std::memset(&fg, 0, sizeof(fg));
+    const int32_t *ip = reinterpret_cast<const int32_t *>(addr);
+    const float *fp = reinterpret_cast<const float *>(addr);
+    float *dg = reinterpret_cast<float *>(addr + 8192);
+    const int32_t d_ff = 2 * d.d_model;
+    CHECK(rom_ffn_backward_workspace_bytes(&d, d_ff, 64) > rom_ffn_workspace_bytes(&d, d_ff, 64));
+    CHECK(rom_ffn_backward_workspace_bytes(&d, 24, 64) == 0);             // d_ff not a multiple of 16
+    CHECK(rom_ffn_backward_workspace_bytes(nullptr, d_ff, 64) == 0);
+    CHECK(rom_ffn_moe_forward(&d, d_ff, nullptr, 1, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr + 4096, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_ffn_moe_forward(&d, d_ff, &fw, 1, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr, addr, 4096, nullptr) == ROM_E_INVAL);       // out == x
+    CHECK(rom_ffn_moe_forward(&d, d_ff, &fw, 1, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr + 4096, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+    CHECK(rom_ffn_moe_backward(&d, d_ff, &fw, fp, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr, addr + 4096, dg, &fg, addr, 4096, nullptr) == ROM_E_INVAL);   // NULL gradient pointers
+    fg.d_w_gate_up = dg; fg.d_w_down = dg;
+    CHECK(rom_ffn_moe_backward(&d, d_ff, &fw, fp, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr, addr + 4096, dg, &fg, addr, 4096, nullptr) == ROM_E_INVAL);   // pre-norm without d_norm_weight
+    fg.d_norm_weight = dg;
+    CHECK(rom_ffn_moe_backward(&d, d_ff, &fw, fp, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr, addr, dg, &fg, addr, 4096, nullptr) == ROM_E_INVAL);          // d_x == x
+    CHECK(rom_ffn_moe_backward(&d, d_ff, &fw, fp, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr, addr + 4096, nullptr, &fg, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_ffn_moe_backward(&d, d_ff, &fw, fp, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr, addr + 4096, dg, &fg, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+    CHECK(rom_ffn_moe_backward(&d, d_ff, &fw, nullptr, 1e-5f, 0, addr, 0, ip, ip, ip, fp, addr, addr + 4096, dg, &fg, addr, 4096, nullptr) == ROM_OK);
+  }
+
   // ---- strings and the profiling bookkeeping
   CHECK(std::strcmp(rom_strerror(ROM_OK), "ok") == 0);
   for (int code : {ROM_E_INVAL, ROM_E_WORKSPACE, ROM_E_UNSUPPORTED, ROM_E_HIP, ROM_E_STATIC_LIMIT, -99})
