@@ -495,8 +495,10 @@ def selective_scan_backward(u, dt, b_mat, c_mat, a, d_skip, d_y, h0=None):
     return {"d_u": d_u, "d_dt": d_dt, "d_b": d_b, "d_c": d_c, "d_a": d_a, "d_d": d_d, "d_h0": d_h}
 
 
-def rom_layer_backward(x, w, top_k, gate_mode, d_out, expert_idx=None):
-    """Gradients of the layer of rom_layer_forward (zero initial states).
+def rom_layer_backward(x, w, top_k, gate_mode, d_out, expert_idx=None, d_gate_extra=None):
+    """Gradients of the layer of rom_layer_forward (zero initial states).  d_gate_extra [N, K]: a
+    gradient with respect to the gate weights that arrives from outside the layer (an FFN-MoE layer
+    running on this layer's routing decision, Eq. (15)); it joins the layer's own before the router.
 
     x [B, L, D_m], d_out [B, L, D_m].  Returns a dict with d_x [B, L, D_m], one d_<name> per
     parameter of `w` (same shapes; d_A_log is with respect to A_log, A = -exp(A_log)), and the
@@ -549,6 +551,8 @@ def rom_layer_backward(x, w, top_k, gate_mode, d_out, expert_idx=None):
     # Eq. (10)/(11)
     d_x, d_w_in = routed_linear_backward(xt, w["w_in"], idx, d_xz)
     # Eq. (9): the gates
+    if d_gate_extra is not None:
+        d_gate = d_gate + np.asarray(d_gate_extra, F64)
     d_logits = gate_weights_backward(fwd["logits"], idx, gate_mode, d_gate)
     d_x = d_x + d_logits @ np.asarray(w["w_router"], F64)
     return {
@@ -575,13 +579,13 @@ def rms_norm_backward(x, weight, eps, d_y):
     return d_x, d_weight
 
 
-def rom_block_backward(x, w, top_k, gate_mode, d_out, eps=1e-5, expert_idx=None):
+def rom_block_backward(x, w, top_k, gate_mode, d_out, eps=1e-5, expert_idx=None, d_gate_extra=None):
     """Gradients of rom_block_forward (zero initial states): the layer's backward on the normalised
     input, the norm's adjoint, and the skip connection's d_out added to d_x.  Returns the dict of
     rom_layer_backward with d_x the block's input gradient and d_norm_w [D_m] added."""
     x = np.asarray(x, F64)
     xn = rms_norm(x, w["norm_w"], eps)
-    res = rom_layer_backward(xn, w, top_k, gate_mode, d_out, expert_idx)
+    res = rom_layer_backward(xn, w, top_k, gate_mode, d_out, expert_idx, d_gate_extra)
     d_x_norm, d_norm_w = rms_norm_backward(x, w["norm_w"], eps, res["d_x"])
     res["d_xn"] = res["d_x"]
     res["d_x"] = np.asarray(d_out, F64) + d_x_norm

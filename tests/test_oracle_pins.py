@@ -881,6 +881,65 @@ def test_ffn_moe_backward_against_library_differentiation(pre_norm, skip, top_k)
     assert pre_norm or "d_norm_w" not in res
 
 
+def test_hybrid_pair_backward_matches_central_differences():
+    """A RoM block followed by an FFN-MoE block on the RoM block's routing decision and gate weights
+    (Eq. (14)/(15)): the chain ffn_moe_backward -> rom_block_backward, with the FFN's gate gradient
+    handed to the block, against central differences of the composed forward - for x, the router
+    (which the FFN reaches through the gates only) and samples of the other parameters."""
+    cfg = tiny_cfg(top_k=2, gate_mode=0, n_experts=4, seq_len=6)
+    w = {k: (None if v is None else np.asarray(v, np.float64)) for k, v in _weights(cfg).items()}
+    rng = np.random.default_rng(37)
+    d_m, d_f = cfg.d_model, 6
+    w["norm_w"] = 1.0 + 0.3 * rng.standard_normal(d_m)
+    fw = {"w_gate_up": 0.5 * rng.standard_normal((4, 2 * d_f, d_m)), "w_down": 0.5 * rng.standard_normal((4, d_m, d_f)),
+          "norm_w": 1.0 + 0.3 * rng.standard_normal(d_m)}
+    x = 1.2 * np.asarray(make_input(cfg), np.float64)
+    n_tok = x.shape[0] * x.shape[1]
+    d_out = rng.standard_normal((n_tok, d_m))
+    idx = O.rom_block_forward(x, w, 2, 0, 1e-5)["expert_idx"]
+
+    def forward(xx, ww, ff):
+        blk = O.rom_block_forward(xx, ww, 2, 0, 1e-5, expert_idx=idx)
+        return blk, O.ffn_moe_forward(blk["out"].reshape(n_tok, d_m), ff["w_gate_up"], ff["w_down"], idx, blk["gate"],
+                                      ff["norm_w"], 1e-5, skip=True)
+
+    blk, _ = forward(x, w, fw)
+    fb = O.ffn_moe_backward(blk["out"].reshape(n_tok, d_m), fw["w_gate_up"], fw["w_down"], idx, blk["gate"], d_out,
+                            fw["norm_w"], 1e-5, skip=True)
+    res = O.rom_block_backward(x, w, 2, 0, fb["d_x"].reshape(x.shape), 1e-5, expert_idx=idx, d_gate_extra=fb["d_gate"])
+    without = O.rom_block_backward(x, w, 2, 0, fb["d_x"].reshape(x.shape), 1e-5, expert_idx=idx)
+    assert np.max(np.abs(res["d_w_router"] - without["d_w_router"])) > 1e-3      # the handed-over gradient matters here
+
+    def loss(xx, ww, ff):
+        return float((forward(xx, ww, ff)[1] * d_out).sum())
+
+    eps = 1e-5
+    for name in ("x", "w_router", "b_router", "w_in", "w_out", "norm_w"):
+        base = x if name == "x" else w[name]
+        grad = res["d_" + name]
+        scale = np.max(np.abs(grad))
+        for _ in range(8):
+            i = tuple(int(rng.integers(0, n)) for n in base.shape)
+            plus, minus = base.copy(), base.copy()
+            plus[i] += eps
+            minus[i] -= eps
+            if name == "x":
+                fd = (loss(plus, w, fw) - loss(minus, w, fw)) / (2 * eps)
+            else:
+                fd = (loss(x, dict(w, **{name: plus}), fw) - loss(x, dict(w, **{name: minus}), fw)) / (2 * eps)
+            assert abs(fd - grad[i]) <= 1e-6 * scale + 1e-8, (name, i, fd, grad[i])
+    for name in ("w_gate_up", "w_down", "norm_w"):
+        base, grad = fw[name], fb["d_" + name]
+        scale = np.max(np.abs(grad))
+        for _ in range(6):
+            i = tuple(int(rng.integers(0, n)) for n in base.shape)
+            plus, minus = base.copy(), base.copy()
+            plus[i] += eps
+            minus[i] -= eps
+            fd = (loss(x, w, dict(fw, **{name: plus})) - loss(x, w, dict(fw, **{name: minus}))) / (2 * eps)
+            assert abs(fd - grad[i]) <= 1e-6 * scale + 1e-8, (name, i, fd, grad[i])
+
+
 def test_scan_backward_closed_forms():
     """Constant coefficients: y_T depends on u_s through C . a^(T-s) . dt B (+ D at s = T), so a
     one-hot d_y at time T gives that as d_u; and the adjoint state after the last step back is
