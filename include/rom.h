@@ -282,15 +282,18 @@ ROM_API int rom_block_forward(const rom_dims *dims, const rom_weights *w, const 
  *   w              the PLAIN weights (w->w_in not folded)
  *   norm_weight    f32 [d_model] (device), eps >= 0
  *   d_norm_weight  f32 [d_model] (device), written
+ *   d_gate_ffn     f32 [B*L, K] (device) or NULL: d loss / d gate from an FFN-MoE layer that ran on this
+ *                  block's routing decision (rom_ffn_moe_backward's d_gate); added to the layer's own
+ *                  gate gradient before the router's backward
  *   ws             rom_block_backward_workspace_bytes(dims, B, L) bytes, 256-byte aligned
  * The call materialises RMSNorm(x) in the activation type, runs the layer's forward and backward on
  * it (rom_layer_backward) and takes the result through the norm's adjoint, adding d_out for the skip.
  * Deterministic; d_model must be a multiple of 4 (ROM_E_UNSUPPORTED otherwise). */
 ROM_API size_t rom_block_backward_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L);
 ROM_API int rom_block_backward(const rom_dims *dims, const rom_weights *w, const float *norm_weight, float eps,
-                               const void *x, int64_t B, int64_t L, const void *d_out, void *d_x,
-                               const rom_grads *grads, float *d_norm_weight, void *ws, size_t ws_bytes,
-                               void *hip_stream);
+                               const void *x, int64_t B, int64_t L, const void *d_out, const float *d_gate_ffn,
+                               void *d_x, const rom_grads *grads, float *d_norm_weight, void *ws,
+                               size_t ws_bytes, void *hip_stream);
 
 /* One new token per sequence through one block; states updated in place (see rom_step). */
 ROM_API int rom_block_step(const rom_dims *dims, const rom_weights *w, const float *norm_weight,

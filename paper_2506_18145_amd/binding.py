@@ -125,7 +125,7 @@ def load_library() -> ctypes.CDLL:
     lib.rom_block_backward_workspace_bytes.restype = SZ
     lib.rom_block_backward_workspace_bytes.argtypes = [ctypes.POINTER(RomDims), I64, I64]
     lib.rom_block_backward.restype = ctypes.c_int
-    lib.rom_block_backward.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, F32, P, I64, I64, P, P,
+    lib.rom_block_backward.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, F32, P, I64, I64, P, P, P,
                                        ctypes.POINTER(_RomGrads), P, P, SZ, P]
     lib.rom_fold_norm.restype = ctypes.c_int
     lib.rom_fold_norm.argtypes = [ctypes.POINTER(RomDims), P, P, P, P]
@@ -306,14 +306,15 @@ def rom_block_backward_workspace_bytes(dims: RomDims, B: int, L: int) -> int:
     return int(load_library().rom_block_backward_workspace_bytes(ctypes.byref(dims), B, L))
 
 
-def rom_block_backward(dims, weights, norm_weight, eps, x, B, L, d_out, d_x, grads, d_norm_weight, ws):
-    """weights: the plain ones (w_in not folded); grads as for rom_layer_backward."""
+def rom_block_backward(dims, weights, norm_weight, eps, x, B, L, d_out, d_x, grads, d_norm_weight, ws, d_gate_ffn=None):
+    """weights: the plain ones (w_in not folded); grads as for rom_layer_backward; d_gate_ffn: the gate
+    gradient of an FFN-MoE layer on this block's routing decision (f32 [B*L, K]) or None."""
     gs = _RomGrads()
     for name, _ in _RomGrads._fields_:
         setattr(gs, name, _ptr(grads.get(name)))
     code = load_library().rom_block_backward(
         ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(norm_weight), eps, _ptr(x), B, L, _ptr(d_out),
-        _ptr(d_x), ctypes.byref(gs), _ptr(d_norm_weight), _ptr(ws), _nbytes(ws), _stream())
+        _ptr(d_gate_ffn), _ptr(d_x), ctypes.byref(gs), _ptr(d_norm_weight), _ptr(ws), _nbytes(ws), _stream())
     _check(code, "rom_block_backward")
 
 
@@ -701,7 +702,7 @@ class RomLayer:
         rom_layer_backward(self.dims, self.weights, x, B, L, d_out, d_x, grads, self._bwd_ws, saved=saved)
         return d_x, grads
 
-    def block_backward(self, x: torch.Tensor, d_out: torch.Tensor, eps: float = 1e-5):
+    def block_backward(self, x: torch.Tensor, d_out: torch.Tensor, eps: float = 1e-5, d_gate_ffn=None):
         """(d_x, grads) of the pre-norm residual block out = x + layer(RMSNorm(x)); grads also holds
         d_norm_w.  Uses the plain weights (the fold of block_weights() is the forward's business)."""
         B, L, _ = x.shape
@@ -718,7 +719,7 @@ class RomLayer:
                 grads[name] = torch.empty(wt.shape, dtype=torch.float32, device=self.device)
         grads["d_norm_w"] = torch.empty(self.dims.d_model, dtype=torch.float32, device=self.device)
         rom_block_backward(self.dims, self.weights, self.weights["norm_w"], eps, x, B, L, d_out, d_x, grads,
-                           grads["d_norm_w"], self._blk_bwd_ws)
+                           grads["d_norm_w"], self._blk_bwd_ws, d_gate_ffn=d_gate_ffn)
         return d_x, grads
 
     def block_backward_xn(self, B: int, L: int) -> torch.Tensor:

@@ -180,6 +180,11 @@ struct StageMark {
     if ((expr) != hipSuccess) return ROM_E_HIP; \
   } while (0)
 
+__global__ void add_f32_kernel(const float *__restrict__ src, float *__restrict__ dst, int64_t n) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] += src[i];
+}
+
 __global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict__ dst, int64_t n) {
   const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
   if (i < n) dst[i] = src[i];
@@ -238,7 +243,11 @@ int route_into(const rom_dims *d, const rom_weights *w, const void *x, int64_t n
 
 int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t B, int64_t L,
                  const float *conv_in, const float *ssm_in, void *out, float *conv_out,
-                 float *ssm_out, void *ws, size_t ws_bytes, hipStream_t s, const BlockOpts *blk = nullptr) {
+                 float *ssm_out, void *ws, size_t ws_bytes, hipStream_t s, const BlockOpts *blk = nullptr,
+                 const void *route_x = nullptr, const BlockOpts *route_blk = nullptr) {
+  // route_x / route_blk: the router alone reads route_x under route_blk's norm (the block's backward:
+  // the decision of the forward block, which normalises x for itself, while everything else runs on
+  // the materialised norm x)
   int rc = check_dims(d);
   if (rc != ROM_OK) return rc;
   rc = check_weights(d, w);
@@ -266,10 +275,11 @@ int forward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t
   const float *rstd = blk ? reinterpret_cast<const float *>(at(p.rstd)) : nullptr;
 
   StageMark mark;
-  rc = route_into(d, w, x, N, reinterpret_cast<int32_t *>(at(p.expert_idx)), gate,
+  rc = route_into(d, w, route_x ? route_x : x, N, reinterpret_cast<int32_t *>(at(p.expert_idx)), gate,
                   reinterpret_cast<int32_t *>(at(p.counts)), offsets, reinterpret_cast<int32_t *>(at(p.perm)),
                   inv_perm, tok_of_pos, reinterpret_cast<int32_t *>(at(p.block_counts)),
-                  reinterpret_cast<float *>(at(p.logits)), blk, reinterpret_cast<float *>(at(p.rstd)), s, &mark,
+                  reinterpret_cast<float *>(at(p.logits)), route_blk ? route_blk : blk,
+                  reinterpret_cast<float *>(at(p.rstd)), s, &mark,
                   p.rank_passes ? reinterpret_cast<int32_t *>(at(p.rank_offsets)) : nullptr,
                   p.rank_passes ? reinterpret_cast<int32_t *>(at(p.rank_tok)) : nullptr,
                   p.rank_passes ? reinterpret_cast<int32_t *>(at(p.rank_blocks)) : nullptr);
@@ -1446,7 +1456,8 @@ size_t rom_backward_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L) 
 
 namespace {
 int backward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t B, int64_t L, const void *d_out,
-                  void *d_x, const rom_grads *gr, void *ws, size_t ws_bytes, void *hip_stream, bool recompute);
+                  void *d_x, const rom_grads *gr, void *ws, size_t ws_bytes, void *hip_stream, bool recompute,
+                  const float *d_gate_extra = nullptr, const void *route_x = nullptr, const BlockOpts *route_blk = nullptr);
 }
 
 int rom_layer_backward(const rom_dims *d, const rom_weights *w, const void *x, int64_t B, int64_t L, const void *d_out,
@@ -1494,8 +1505,8 @@ size_t rom_block_backward_workspace_bytes(const rom_dims *d, int64_t B, int64_t 
 }
 
 int rom_block_backward(const rom_dims *d, const rom_weights *w, const float *norm_weight, float eps, const void *x,
-                       int64_t B, int64_t L, const void *d_out, void *d_x, const rom_grads *gr, float *d_norm_weight,
-                       void *ws, size_t ws_bytes, void *hip_stream) {
+                       int64_t B, int64_t L, const void *d_out, const float *d_gate_ffn, void *d_x, const rom_grads *gr,
+                       float *d_norm_weight, void *ws, size_t ws_bytes, void *hip_stream) {
   int rc = check_dims(d);
   if (rc != ROM_OK) return rc;
   if (!norm_weight || !aligned16(norm_weight) || !(eps >= 0.0f) || !d_norm_weight) return ROM_E_INVAL;
@@ -1514,7 +1525,13 @@ int rom_block_backward(const rom_dims *d, const rom_weights *w, const float *nor
   // the layer's backward runs on the materialised norm (the forward block never forms it: its in
   // projection scales rows of x W'^T instead, which differs by the rounding of xn to the type)
   ROM_TRY(launch_rmsnorm_forward(d->dtype, x, norm_weight, eps, N, d->d_model, base + p.xn, rstd, s));
-  rc = backward_impl(d, w, base + p.xn, B, L, d_out, base + p.d_xn, gr, ws, p.inner, hip_stream, true);
+  // the router reads the raw x and normalises it itself, exactly as in rom_block_forward: the backward
+  // differentiates the expert choice the forward made (a router fed the rounded norm could pick
+  // another expert for a token whose two best logits are nearly equal)
+  BlockOpts opts;
+  opts.norm_w = norm_weight;
+  opts.eps = eps;
+  rc = backward_impl(d, w, base + p.xn, B, L, d_out, base + p.d_xn, gr, ws, p.inner, hip_stream, true, d_gate_ffn, x, &opts);
   if (rc != ROM_OK) return rc;
   ROM_TRY(launch_rmsnorm_backward(d->dtype, x, norm_weight, rstd, base + p.d_xn, d_out, N, d->d_model, d_x,
                                   reinterpret_cast<float *>(base + p.part), d_norm_weight, s));
@@ -1523,7 +1540,8 @@ int rom_block_backward(const rom_dims *d, const rom_weights *w, const float *nor
 
 namespace {
 int backward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_t B, int64_t L, const void *d_out,
-                  void *d_x, const rom_grads *gr, void *ws, size_t ws_bytes, void *hip_stream, bool recompute) {
+                  void *d_x, const rom_grads *gr, void *ws, size_t ws_bytes, void *hip_stream, bool recompute,
+                  const float *d_gate_extra, const void *route_x, const BlockOpts *route_blk) {
   int rc = check_dims(d);
   if (rc != ROM_OK) return rc;
   rc = check_weights(d, w);
@@ -1553,7 +1571,8 @@ int backward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_
   // activations: the forward pass into the front part of the workspace, unless the caller's own
   // rom_layer_forward call on this workspace has just left them there
   if (recompute) {
-    rc = forward_impl(d, w, x, B, L, nullptr, nullptr, at(bp.fwd_out), nullptr, nullptr, ws, p.total, s);
+    rc = forward_impl(d, w, x, B, L, nullptr, nullptr, at(bp.fwd_out), nullptr, nullptr, ws, p.total, s, nullptr, route_x,
+                      route_blk);
     if (rc != ROM_OK) return rc;
   }
   const int32_t *offsets = reinterpret_cast<const int32_t *>(at(p.offsets));
@@ -1669,7 +1688,11 @@ int backward_impl(const rom_dims *d, const rom_weights *w, const void *x, int64_
                multi ? at(bp.pos_dm) : nullptr, w->w_in));
   ROM_TRY(wgrad(at(bp.d_xz), 2 * De, false, 2 * De, x, Dm, Dm, E, gr->d_w_in));
 #undef ROM_RC
-  // Eq. (9): the router through the gate weights
+  // Eq. (9): the router through the gate weights (plus what an FFN-MoE layer on this decision sends back, Eq. (15))
+  if (d_gate_extra) {
+    hipLaunchKernelGGL(add_f32_kernel, dim3(static_cast<unsigned>(ceil_div(S, 256))), dim3(256), 0, s, d_gate_extra, d_gate, S);
+    ROM_TRY(hipGetLastError());
+  }
   ROM_TRY(launch_router_backward(d->dtype, reinterpret_cast<const float *>(at(p.logits)),
                                  reinterpret_cast<const int32_t *>(at(p.expert_idx)), d_gate, x, N, Dm, E, K,
                                  d->gate_mode, d_logits, reinterpret_cast<float *>(at(bp.router_part)), gr->d_w_router,

@@ -122,12 +122,12 @@ int main() {
       float *dnw = reinterpret_cast<float *>(addr + 8192);
       CHECK(rom_block_backward_workspace_bytes(&d, 1, 8) > rom_backward_workspace_bytes(&d, 1, 8));
       CHECK(rom_block_backward_workspace_bytes(nullptr, 1, 8) == 0);
-      CHECK(rom_block_backward(&d, &w, nullptr, 1e-5f, addr, 1, 8, addr, addr + 4096, &g, dnw, addr, 4096, nullptr) == ROM_E_INVAL);
-      CHECK(rom_block_backward(&d, &w, nw, -1.0f, addr, 1, 8, addr, addr + 4096, &g, dnw, addr, 4096, nullptr) == ROM_E_INVAL);
-      CHECK(rom_block_backward(&d, &w, nw, 1e-5f, addr, 1, 8, addr, addr + 4096, &g, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
-      CHECK(rom_block_backward(&d, &w, nw, 1e-5f, addr, 1, 8, addr, addr, &g, dnw, addr, 4096, nullptr) == ROM_E_INVAL);        // d_x == x
-      CHECK(rom_block_backward(&d, &w, nw, 1e-5f, addr, 1, 8, addr, addr + 4096, &g, dnw, addr, 4096, nullptr) == ROM_E_WORKSPACE);
-      CHECK(rom_block_backward(&d, &w, nw, 1e-5f, addr, 0, 8, addr, addr + 4096, &g, dnw, addr, 4096, nullptr) == ROM_OK);
+      CHECK(rom_block_backward(&d, &w, nullptr, 1e-5f, addr, 1, 8, addr, nullptr, addr + 4096, &g, dnw, addr, 4096, nullptr) == ROM_E_INVAL);
+      CHECK(rom_block_backward(&d, &w, nw, -1.0f, addr, 1, 8, addr, nullptr, addr + 4096, &g, dnw, addr, 4096, nullptr) == ROM_E_INVAL);
+      CHECK(rom_block_backward(&d, &w, nw, 1e-5f, addr, 1, 8, addr, nullptr, addr + 4096, &g, nullptr, addr, 4096, nullptr) == ROM_E_INVAL);
+      CHECK(rom_block_backward(&d, &w, nw, 1e-5f, addr, 1, 8, addr, nullptr, addr, &g, dnw, addr, 4096, nullptr) == ROM_E_INVAL);        // d_x == x
+      CHECK(rom_block_backward(&d, &w, nw, 1e-5f, addr, 1, 8, addr, nullptr, addr + 4096, &g, dnw, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+      CHECK(rom_block_backward(&d, &w, nw, 1e-5f, addr, 0, 8, addr, nullptr, addr + 4096, &g, dnw, addr, 4096, nullptr) == ROM_OK);
     }
     // workspace too small
     CHECK(rom_layer_forward(&d, &w, addr, 1, 8, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 16, nullptr) == ROM_E_WORKSPACE);

@@ -162,10 +162,10 @@ def test_block_backward(kw, scale):
     layer._ws = layer._blk_bwd_ws
     gpu = {k: to_np(layer.ws_view(k, B, L)) for k in ("expert_idx", "gate", "counts", "offsets", "perm", "inv_perm", "logits")}
     layer._ws = ws_keep
-    # the materialised norm against the oracle's, then the routing on exactly what the router saw
+    # the materialised norm against the oracle's; the router normalises the raw x itself, as the forward block does
     xn = to_np(layer.block_backward_xn(B, L))
     assert rel_err(xn, O.rms_norm(x, w["norm_w"], 1e-5)) <= (2.0 ** -8 if cfg.dtype == "bf16" else 1e-6)
-    idx, n_excl = check_routing(cfg, gpu, xn, w)
+    idx, n_excl = check_routing(cfg, gpu, x, w, block=True)
     ref = O.rom_block_backward(x, w, cfg.top_k, cfg.gate_mode, d_out, 1e-5, expert_idx=idx)
     tol = TOL[cfg.dtype]
     errs = {"d_x": rel_err(to_np(d_x), ref["d_x"]), "d_norm_w": rel_err(to_np(grads["d_norm_w"]), ref["d_norm_w"])}
@@ -247,3 +247,56 @@ def test_ffn_moe_backward(kw, d_ff, pre_norm, add_skip):
 def test_ffn_moe_backward_full_size():
     _ffn_backward_case(get_config("cfg2"), 4096, True, True)
     _ffn_backward_case(get_config("cfg1"), 2048, True, False)      # and a branch that no skip term can mask
+
+
+@pytest.mark.parametrize("kw", [dict(cfg_id=190), dict(cfg_id=191, dtype="fp32", seq_len=90),
+                                dict(cfg_id=192, top_k=2, gate_mode=1, n_experts=8)])
+def test_hybrid_pair_backward_chain(kw):
+    """A RoM block, then an FFN-MoE block on its routing decision (pre-norm + skip both): the training
+    step's backward chain rom_ffn_moe_backward -> rom_block_backward(d_gate_ffn = the FFN's gate
+    gradient), against the oracle's chain on the same expert choice.  The router's gradient is where a
+    dropped or mis-scaled hand-over would show."""
+    cfg = small_cfg(weight_std=0.08, **kw)
+    d_ff = 384
+    w, fw, x = make_weights(cfg), make_ffn_weights(cfg, d_ff), make_input(cfg)
+    if w["b_router"] is None:
+        w["b_router"] = np.zeros(cfg.n_experts, np.float32)
+    rng = np.random.default_rng(cfg.cfg_id)
+    w["norm_w"] = (1.0 + 0.3 * rng.standard_normal(cfg.d_model)).astype(np.float32)
+    layer = RomLayer(cfg, w)
+    ffn = RomFfnMoe(layer, d_ff, fw, eps=1e-5)
+    B, L = cfg.batch, cfg.seq_len
+    N = B * L
+    xd = layer.to_device(x)
+    d_out = _d_out(cfg, x.shape)
+    dd = layer.to_device(d_out)
+    # forward of the pair (the block leaves its routing decision in the layer's workspace)
+    mid = layer.block_forward(xd, eps=1e-5)
+    routing = {k: layer.ws_view(k, B, L).clone() for k in ("offsets", "perm", "inv_perm", "gate", "expert_idx")}
+    # backward: FFN first, its input gradient and gate gradient go to the block
+    d_mid, d_gate_ffn, fg = ffn.backward(mid.view(N, -1), routing, dd.view(N, -1), pre_norm=True, add_skip=True)
+    d_x, grads = layer.block_backward(xd, d_mid.view(B, L, -1), eps=1e-5, d_gate_ffn=d_gate_ffn)
+    torch.cuda.synchronize()
+    idx = to_np(routing["expert_idx"])
+    # the block backward recomputes the routing on its materialised norm: it must agree with the forward's
+    ws_keep = layer._ws
+    layer._ws = layer._blk_bwd_ws
+    assert np.array_equal(to_np(layer.ws_view("expert_idx", B, L)), idx)
+    layer._ws = ws_keep
+    blk = O.rom_block_forward(x, w, cfg.top_k, cfg.gate_mode, 1e-5, expert_idx=idx)
+    fb = O.ffn_moe_backward(blk["out"].reshape(N, -1), fw["w_gate_up"], fw["w_down"], idx, blk["gate"],
+                            d_out.reshape(N, -1), fw["norm_w"], 1e-5, skip=True)
+    ref = O.rom_block_backward(x, w, cfg.top_k, cfg.gate_mode, fb["d_x"].reshape(x.shape), 1e-5, expert_idx=idx,
+                               d_gate_extra=fb["d_gate"])
+    alone = O.rom_block_backward(x, w, cfg.top_k, cfg.gate_mode, fb["d_x"].reshape(x.shape), 1e-5, expert_idx=idx)
+    errs = {"d_x": rel_err(to_np(d_x), ref["d_x"]), "d_norm_w": rel_err(to_np(grads["d_norm_w"]), ref["d_norm_w"]),
+            "d_gate_ffn": rel_err(to_np(d_gate_ffn), fb["d_gate"]),
+            "ffn d_w_down": rel_err(to_np(fg["d_w_down"]), fb["d_w_down"])}
+    for name in PARAMS:
+        errs["d_" + name] = rel_err(to_np(grads["d_" + name]), ref["d_" + name])
+    share = float(np.max(np.abs(ref["d_w_router"] - alone["d_w_router"])) / np.max(np.abs(ref["d_w_router"])))
+    print(f"[pair {cfg.name}] ffn share of d_w_router={share:.2f} " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()),
+          flush=True)
+    assert share > 0.1, "the FFN's gate gradient is too small here to test the hand-over"
+    bad = {k: v for k, v in errs.items() if not v <= TOL[cfg.dtype]}
+    assert not bad, bad
