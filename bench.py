@@ -405,6 +405,16 @@ def backward_rate(cfg, steps, warmup):
         evs[i + 1].record()
     torch.cuda.synchronize()
     ms_step = _median([evs[i].elapsed_time(evs[i + 1]) for i in range(steps)])
+    # the pre-norm residual block's backward (materialised norm, layer forward + backward on it, norm adjoint + skip)
+    for _ in range(2):
+        layer.block_backward(x, d_out)
+    torch.cuda.synchronize()
+    evs[0].record()
+    for i in range(steps):
+        d_xb, _ = layer.block_backward(x, d_out)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    ms_block = _median([evs[i].elapsed_time(evs[i + 1]) for i in range(steps)])
     n_tok = cfg.batch * cfg.seq_len
     S = n_tok * cfg.top_k
     Sx = S if cfg.routed_xdt else n_tok
@@ -415,6 +425,7 @@ def backward_rate(cfg, steps, warmup):
                         "w.r.t. x and all parameters; training_step = rom_layer_forward + rom_layer_backward_saved",
             "ms_per_call": ms, "tokens_per_s": n_tok / (ms * 1e-3),
             "ms_per_training_step": ms_step, "training_tokens_per_s": n_tok / (ms_step * 1e-3),
+            "ms_per_block_backward_call": ms_block,
             "gemm_tflops_forward_plus_backward": 3.0 * gemm / (ms * 1e-3) / 1e12, "gradients_finite": finite}
 
 
