@@ -220,7 +220,7 @@ def ffn_moe_rate(cfg, d_ff, steps, warmup):
             "backward": {"workload": "rom_ffn_moe_backward: forward recomputation + gradients w.r.t. x, the gate weights, "
                                      "the norm scale and both expert weights",
                          "ms_per_call": ms_bwd, "tokens_per_s": n_tok / (ms_bwd * 1e-3),
-                         "gemm_tflops": 4.0 * flops / (ms_bwd * 1e-3) / 1e12,
+                         "gemm_tflops": 3.0 * flops / (ms_bwd * 1e-3) / 1e12,     # recomputed forward + four adjoint GEMMs = 3 x forward
                          "gradients_finite": bool(torch.isfinite(d_x.float()).all().item())}}
 
 
