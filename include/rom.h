@@ -500,7 +500,8 @@ ROM_API int rom_mamba2_forward(const rom_mamba2_dims *dims, const rom_mamba2_wei
  * itself, the input projection runs on the raw x with w->w_in FOLDED (rom_fold_norm_rows over its
  * E * (2*d_inner + 2*d_state + n_heads) rows) and scales its rows by 1/rms, the skip is added where the
  * output projection or the combine writes out.  out must not alias x (ROM_E_INVAL).  Everything else
- * as rom_mamba2_forward. */
+ * as rom_mamba2_forward; with L == 1 and the states passed as both input and output (allowed up to
+ * L == 32) the call is the block's recurrent step. */
 ROM_API int rom_mamba2_block_forward(const rom_mamba2_dims *dims, const rom_mamba2_weights *w,
                                      const float *norm_weight, float norm_eps, const void *x, int64_t B,
                                      int64_t L, float eps, const float *conv_state_in,

@@ -10,7 +10,8 @@ from gpu_util import BLOCK_EPS, TOL, check_routing, rel_err, to_np
 from oracle import rom_gdn_oracle as G
 from oracle import rom_mamba2_oracle as M
 from oracle import rom_oracle as O
-from paper_2506_18145_amd import RomGdnLayer, RomMamba2Layer, rom_fold_norm_rows
+from paper_2506_18145_amd import (RomGdnLayer, RomMamba2Layer, rom_fold_norm_rows, rom_gdn_block_forward,
+                                  rom_mamba2_block_forward)
 from rom_synth import (get_gdn_config, get_mamba2_config, make_gdn_input, make_gdn_weights, make_mamba2_input,
                        make_mamba2_weights, round_to_bf16)
 
@@ -113,3 +114,50 @@ def test_fold_norm_rows_scales_the_columns():
         rom_fold_norm_rows(code, src, s, dst, 37, 200)
         torch.cuda.synchronize()
         assert torch.equal(dst, (src.float() * s).to(dt))
+
+
+@pytest.mark.parametrize("kind", ["mamba2", "gdn"])
+def test_variant_block_decodes_one_token_at_a_time(kind):
+    """The block call with L = 1 and the states passed as both input and output is the block's
+    recurrent step: 40 steps against the oracle's block on the whole sequence."""
+    if kind == "mamba2":
+        cfg = get_mamba2_config("m2_small", batch=3, seq_len=40, cfg_id=67, weight_std=0.05)
+        w_np, x_np = make_mamba2_weights(cfg), make_mamba2_input(cfg)
+        layer = RomMamba2Layer(cfg, w_np, eps=EPS)
+    else:
+        cfg = get_gdn_config("gdn_small", batch=3, seq_len=40, cfg_id=67, weight_std=0.1)
+        w_np, x_np = make_gdn_weights(cfg), make_gdn_input(cfg)
+        layer = RomGdnLayer(cfg, w_np, eps=EPS)
+    x_np = round_to_bf16(x_np * np.float32(1.3))
+    pre_w = _pre_norm_weight(cfg)
+    pre_w_d = torch.from_numpy(pre_w).cuda()
+    x = layer.to_device(x_np)
+    B, L = cfg.batch, cfg.seq_len
+    cshape, sshape = layer.state_shapes(B)
+    cs = torch.zeros(cshape, dtype=torch.float32, device="cuda")
+    ss = torch.zeros(sshape, dtype=torch.float32, device="cuda")
+    outs, idxs = [], []
+    for t in range(L):
+        xt = x[:, t:t + 1].contiguous()
+        out = torch.empty_like(xt)
+        fn = rom_mamba2_block_forward if kind == "mamba2" else rom_gdn_block_forward
+        fn(layer.dims, layer.block_weights(pre_w_d), pre_w_d, BLOCK_EPS, xt, B, 1, layer.eps, cs, ss, out, cs, ss,
+           layer.workspace(B, 1))
+        outs.append(to_np(out)[:, 0])
+        idxs.append(to_np(layer.ws_view("expert_idx", B, 1)).reshape(B, -1))
+    torch.cuda.synchronize()
+    got = np.stack(outs, axis=1)
+    idx = np.stack(idxs, axis=1).reshape(B * L, -1)
+    xn = O.rms_norm(x_np, pre_w, BLOCK_EPS)
+    logits = O.router_logits(xn.reshape(B * L, -1), w_np["w_router"], w_np.get("b_router"))
+    close = O.topk_margin(logits, cfg.top_k) < 1e-5
+    assert np.array_equal(idx[~close], O.topk_select(logits, cfg.top_k)[~close])
+    if kind == "mamba2":
+        ref = M.rom_mamba2_forward(xn, w_np, cfg.top_k, cfg.gate_mode, cfg.headdim, EPS, expert_idx=idx)
+    else:
+        ref = G.rom_gdn_forward(xn, w_np, cfg.top_k, cfg.gate_mode, cfg.n_heads, cfg.d_k, EPS, expert_idx=idx)
+    want = np.asarray(x_np, np.float64) + ref["out"]
+    errs = {"out": rel_err(got, want), "conv_state": rel_err(to_np(cs), ref["conv_state"]),
+            "ssm_state": rel_err(to_np(ss), ref["ssm_state"].transpose(0, 1, 3, 2))}
+    print(f"[{kind} block steps] " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    assert all(v <= TOL["bf16"] for v in errs.values()), errs
