@@ -214,7 +214,34 @@ def ffn_moe_rate(cfg, d_ff, steps, warmup):
     e1.record()
     torch.cuda.synchronize()
     ms_bwd = e0.elapsed_time(e1) / n_bwd
+    # one training step of the hybrid pair of the appendix: RoM block forward, FFN-MoE block forward on its
+    # routing decision, then the two backward calls (the FFN's gate gradient handed to the block)
+    B, L = cfg.batch, cfg.seq_len
+    x3 = x.view(B, L, Dm)
+    names = ("offsets", "perm", "inv_perm", "gate")
+
+    def pair_step():
+        mid = layer.block_forward(x3, eps=1e-5)
+        r = {k: layer.ws_view(k, B, L) for k in names}
+        ffn.forward(mid.view(-1, Dm), r, pre_norm=True, add_skip=True, out=out)
+        d_mid, d_gate_ffn, _ = ffn.backward(mid.view(-1, Dm), r, d_out, pre_norm=True, add_skip=True)
+        return layer.block_backward(x3, d_mid.view(B, L, Dm), eps=1e-5, d_gate_ffn=d_gate_ffn)[0]
+
+    for _ in range(2):
+        pair_step()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(n_bwd):
+        d_xp = pair_step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_pair = e0.elapsed_time(e1) / n_bwd
     return {"workload": f"{cfg.name}'s tokens and routing, SwiGLU experts d_ff={d_ff}, pre-norm + skip",
+            "hybrid_pair_training_step": {
+                "workload": "rom_block_forward + rom_ffn_moe_forward + rom_ffn_moe_backward + rom_block_backward "
+                            "(both backward calls recompute their forward), no optimizer",
+                "ms_per_step": ms_pair, "tokens_per_s": n_tok / (ms_pair * 1e-3),
+                "gradients_finite": bool(torch.isfinite(d_xp.float()).all().item())},
             "ms_per_call": ms, "tokens_per_s": n_tok / (ms * 1e-3), "bound": "mfma",
             "achieved_tflops": flops / (ms * 1e-3) / 1e12, "frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "backward": {"workload": "rom_ffn_moe_backward: forward recomputation + gradients w.r.t. x, the gate weights, "
@@ -369,6 +396,17 @@ def time_forward(cfg, steps, warmup, with_balance=True):
         ach = fl / (stages["scan_gate"]["ms"] * 1e-3) / 1e12
         stages["scan_gate"].update({"alu_tflops": ach, "alu_frac": ach / PEAK_ALU_FP32_TFLOPS,
                                     "alu_peak_tflops": PEAK_ALU_FP32_TFLOPS})
+    # the two narrow projections move far more bytes than their flops can hide: the x projection reads all
+    # of u for 160 output columns, the dt projection writes all of dt from 128 input columns.  Next to their
+    # MFMA fraction, their algorithmic HBM bytes against the HBM peak.
+    b = 2 if cfg.dtype == "bf16" else 4
+    Sx = n_tok * cfg.top_k if cfg.routed_xdt else n_tok
+    narrow = {"x_proj": Sx * cfg.d_inner * b + Sx * (cfg.dt_rank + 2 * cfg.d_state) * 4,
+              "dt_proj": Sx * cfg.dt_rank * b + n_tok * cfg.d_inner * b}
+    for name, nbytes in narrow.items():
+        if stages[name].get("ms", 0) > 0:
+            gbs = nbytes / (stages[name]["ms"] * 1e-3) / 1e9
+            stages[name].update({"hbm_gbs": gbs, "hbm_frac": gbs / PEAK_HBM_GBS})
     res["stages"] = stages
     return res
 
