@@ -38,7 +38,7 @@ NOMINAL_CLOCK_GHZ = 2.4
 # (profiles/forward_cfg2_hbm_traffic.md: 1.06e6 cycles per XCD in 0.543 ms): the published peaks
 # assume 2.4 GHz, the chip sustains less under a bf16 GEMM of N(0,1)-like operands
 COUNTER_CLOCK_GHZ_GEMM = 1.95
-DOMINANT_KERNEL = "gemm_bf16_dma_kernel<256, 4, 2, 0>"     # the in projection at top-1
+DOMINANT_KERNEL = "gemm_bf16_dma_kernel<256, 4, 2, 0, false>"     # the in projection at top-1
 DOMINANT_STAGE = "in_proj"
 
 
