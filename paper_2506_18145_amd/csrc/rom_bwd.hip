@@ -1214,26 +1214,27 @@ __global__ __launch_bounds__(512) void wgrad_bf16_dma_kernel(const bf16_t *__res
     }
     const unsigned lda2 = static_cast<unsigned>(lda) * 2, ldb2 = static_cast<unsigned>(ldb) * 2;
 
-    // the eight operand rows a wave brings for half slab h (uniform: scalar loads)
-    auto row_idx = [&](int h, unsigned (&off)[8]) __attribute__((always_inline)) {
+    // the eight operand rows a wave brings for half slab h (uniform: scalar loads; the index only - its
+    // first use, the multiply in issue(), is where the compiler waits for the load)
+    auto row_idx = [&](int h, unsigned (&row)[8]) __attribute__((always_inline)) {
       const int m = h >> 1, sl = m < KT ? m : KT - 1;             // past the end: harmless reload
       const int64_t pb = p_lo + static_cast<int64_t>(sl) * kWgSlab + wave * 8;
       const int32_t *rows = (h & 1) ? rows_b : rows_a;
-      const unsigned ld2 = (h & 1) ? ldb2 : lda2;
       const bool mapped = (h & 1) ? MAP_B : MAP_A;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int64_t pp = pb + i < n_pos ? pb + i : n_pos - 1;
-        const unsigned r = mapped ? static_cast<unsigned>(rows[pp]) : static_cast<unsigned>(pp);
-        off[i] = r * ld2;                                         // (the launcher checks that this fits 32 bits)
+        row[i] = mapped ? static_cast<unsigned>(rows[pp]) : static_cast<unsigned>(pp);
       }
     };
-    auto issue = [&](int h, const unsigned (&off)[8]) __attribute__((always_inline)) {
+    auto issue = [&](int h, const unsigned (&row)[8]) __attribute__((always_inline)) {
       const unsigned slot = lds_wave + static_cast<unsigned>(h % kWdSlots) * kWdSlotBytes;
       const void *base = (h & 1) ? static_cast<const void *>(Bm) : static_cast<const void *>(A);
+      const unsigned ld2 = (h & 1) ? ldb2 : lda2;
 #pragma unroll
       for (int j = 0; j < kWdInstr; ++j) {
-        const unsigned voff = (half ? off[2 * j + 1] : off[2 * j]) + ((h & 1) ? col_b[j] : col_a[j]);
+        // (the launcher checks that row * ld2 fits 32 bits)
+        const unsigned voff = (half ? row[2 * j + 1] : row[2 * j]) * ld2 + ((h & 1) ? col_b[j] : col_a[j]);
         wd_dma_16(slot + j * 1024, voff, base);
       }
     };
@@ -1302,6 +1303,9 @@ __global__ __launch_bounds__(512) void wgrad_bf16_dma_kernel(const bf16_t *__res
       unsigned off_b[8], off_a[8];
       row_idx(2 * m + kWdSlots, off_b);                           // B(m+2) and A(m+3), issued after this slab
       row_idx(2 * m + kWdSlots + 1, off_a);
+      // the index loads leave now, a slab's worth of MFMAs before they are used (left to itself the
+      // scheduler sinks them to their use behind the barrier, a scalar-memory round trip per slab)
+      __builtin_amdgcn_sched_barrier(0);
       load_frags(m, 1, fa1, fb1);
       mma(fa0, fb0);
       load_frags(m, 2, fa0, fb0);
