@@ -221,11 +221,11 @@ def ffn_moe_rate(cfg, d_ff, steps, warmup):
     names = ("offsets", "perm", "inv_perm", "gate")
 
     def pair_step():
-        mid = layer.block_forward(x3, eps=1e-5)
-        r = {k: layer.ws_view(k, B, L) for k in names}
-        ffn.forward(mid.view(-1, Dm), r, pre_norm=True, add_skip=True, out=out)
-        d_mid, d_gate_ffn, _ = ffn.backward(mid.view(-1, Dm), r, d_out, pre_norm=True, add_skip=True)
-        return layer.block_backward(x3, d_mid.view(B, L, Dm), eps=1e-5, d_gate_ffn=d_gate_ffn)[0]
+        mid = layer.block_forward_train(x3, eps=1e-5)
+        r = {k: layer.train_routing_view(k, B, L) for k in names}
+        ffn.forward_train(mid.view(-1, Dm), r, pre_norm=True, add_skip=True, out=out)
+        d_mid, d_gate_ffn, _ = ffn.backward(mid.view(-1, Dm), r, d_out, pre_norm=True, add_skip=True, saved=True)
+        return layer.block_backward(x3, d_mid.view(B, L, Dm), eps=1e-5, d_gate_ffn=d_gate_ffn, saved=True)[0]
 
     for _ in range(2):
         pair_step()
@@ -238,8 +238,8 @@ def ffn_moe_rate(cfg, d_ff, steps, warmup):
     ms_pair = e0.elapsed_time(e1) / n_bwd
     return {"workload": f"{cfg.name}'s tokens and routing, SwiGLU experts d_ff={d_ff}, pre-norm + skip",
             "hybrid_pair_training_step": {
-                "workload": "rom_block_forward + rom_ffn_moe_forward + rom_ffn_moe_backward + rom_block_backward "
-                            "(both backward calls recompute their forward), no optimizer",
+                "workload": "rom_block_forward_train + rom_ffn_moe_forward_train + rom_ffn_moe_backward_saved + "
+                            "rom_block_backward_saved (activations kept between forward and backward), no optimizer",
                 "ms_per_step": ms_pair, "tokens_per_s": n_tok / (ms_pair * 1e-3),
                 "gradients_finite": bool(torch.isfinite(d_xp.float()).all().item())},
             "ms_per_call": ms, "tokens_per_s": n_tok / (ms * 1e-3), "bound": "mfma",

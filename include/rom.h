@@ -288,12 +288,27 @@ ROM_API int rom_block_forward(const rom_dims *dims, const rom_weights *w, const 
  *   ws             rom_block_backward_workspace_bytes(dims, B, L) bytes, 256-byte aligned
  * The call materialises RMSNorm(x) in the activation type, runs the layer's forward and backward on
  * it (rom_layer_backward) and takes the result through the norm's adjoint, adding d_out for the skip.
- * Deterministic; d_model must be a multiple of 4 (ROM_E_UNSUPPORTED otherwise). */
+ * Deterministic. */
 ROM_API size_t rom_block_backward_workspace_bytes(const rom_dims *dims, int64_t B, int64_t L);
 ROM_API int rom_block_backward(const rom_dims *dims, const rom_weights *w, const float *norm_weight, float eps,
                                const void *x, int64_t B, int64_t L, const void *d_out, const float *d_gate_ffn,
                                void *d_x, const rom_grads *grads, float *d_norm_weight, void *ws,
                                size_t ws_bytes, void *hip_stream);
+
+/* The two halves of that call for a training step that needs the block's output before it has d_out:
+ * rom_block_forward_train computes out = x + RoM(RMSNorm(x)) with the arithmetic the backward
+ * recomputes (materialised norm in the activation type, PLAIN weights) and leaves every activation
+ * in ws; rom_block_backward_saved then runs the backward pass alone.  Same ws
+ * (rom_block_backward_workspace_bytes), same x, weights, norm_weight and eps, nothing else writing
+ * to ws in between; the routing decision is in ws at the offsets of rom_workspace_layout.  Results
+ * identical to rom_block_backward, bit for bit.  out must not alias x. */
+ROM_API int rom_block_forward_train(const rom_dims *dims, const rom_weights *w, const float *norm_weight,
+                                    float eps, const void *x, int64_t B, int64_t L, void *out, void *ws,
+                                    size_t ws_bytes, void *hip_stream);
+ROM_API int rom_block_backward_saved(const rom_dims *dims, const rom_weights *w, const float *norm_weight,
+                                     float eps, const void *x, int64_t B, int64_t L, const void *d_out,
+                                     const float *d_gate_ffn, void *d_x, const rom_grads *grads,
+                                     float *d_norm_weight, void *ws, size_t ws_bytes, void *hip_stream);
 
 /* One new token per sequence through one block; states updated in place (see rom_step). */
 ROM_API int rom_block_step(const rom_dims *dims, const rom_weights *w, const float *norm_weight,
@@ -392,6 +407,23 @@ ROM_API int rom_ffn_moe_backward(const rom_dims *dims, int32_t d_ff, const rom_f
                                  const int32_t *offsets, const int32_t *perm, const int32_t *inv_perm,
                                  const float *gate, const void *d_out, void *d_x, float *d_gate,
                                  const rom_ffn_grads *grads, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* The two halves of that call for a training step: rom_ffn_moe_forward_train computes the layer's output
+ * (out T [N, d_model], must not alias x) with the pre-activations, the experts' inputs and outputs
+ * kept in ws; rom_ffn_moe_backward_saved then runs the backward pass alone on the same ws
+ * (rom_ffn_backward_workspace_bytes), same arguments, nothing else writing to ws in between.
+ * Gradients identical to rom_ffn_moe_backward, bit for bit. */
+ROM_API int rom_ffn_moe_forward_train(const rom_dims *dims, int32_t d_ff, const rom_ffn_weights *w,
+                                      const float *norm_weight, float eps, int add_skip, const void *x,
+                                      int64_t N, const int32_t *offsets, const int32_t *perm,
+                                      const int32_t *inv_perm, const float *gate, void *out, void *ws,
+                                      size_t ws_bytes, void *hip_stream);
+ROM_API int rom_ffn_moe_backward_saved(const rom_dims *dims, int32_t d_ff, const rom_ffn_weights *w,
+                                       const float *norm_weight, float eps, int add_skip, const void *x,
+                                       int64_t N, const int32_t *offsets, const int32_t *perm,
+                                       const int32_t *inv_perm, const float *gate, const void *d_out,
+                                       void *d_x, float *d_gate, const rom_ffn_grads *grads, void *ws,
+                                       size_t ws_bytes, void *hip_stream);
 
 /* The hybrid of the appendix (RoM + FFN-MoE with shared routing), as a stack: layer j is the RoM
  * block blocks[j]; if ffns[j].w_gate_up is not NULL an FFN-MoE block (pre-norm if ffn_pre_norm,

@@ -127,6 +127,11 @@ def load_library() -> ctypes.CDLL:
     lib.rom_block_backward.restype = ctypes.c_int
     lib.rom_block_backward.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, F32, P, I64, I64, P, P, P,
                                        ctypes.POINTER(_RomGrads), P, P, SZ, P]
+    lib.rom_block_backward_saved.restype = ctypes.c_int
+    lib.rom_block_backward_saved.argtypes = lib.rom_block_backward.argtypes
+    lib.rom_block_forward_train.restype = ctypes.c_int
+    lib.rom_block_forward_train.argtypes = [ctypes.POINTER(RomDims), ctypes.POINTER(_RomWeights), P, F32, P, I64, I64, P, P,
+                                            SZ, P]
     lib.rom_fold_norm.restype = ctypes.c_int
     lib.rom_fold_norm.argtypes = [ctypes.POINTER(RomDims), P, P, P, P]
     lib.rom_block_forward.restype = ctypes.c_int
@@ -153,6 +158,11 @@ def load_library() -> ctypes.CDLL:
     lib.rom_ffn_moe_backward.restype = ctypes.c_int
     lib.rom_ffn_moe_backward.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, ctypes.POINTER(_RomFfnWeights), P, F32,
                                          ctypes.c_int, P, I64, P, P, P, P, P, P, P, ctypes.POINTER(_RomFfnGrads), P, SZ, P]
+    lib.rom_ffn_moe_backward_saved.restype = ctypes.c_int
+    lib.rom_ffn_moe_backward_saved.argtypes = lib.rom_ffn_moe_backward.argtypes
+    lib.rom_ffn_moe_forward_train.restype = ctypes.c_int
+    lib.rom_ffn_moe_forward_train.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, ctypes.POINTER(_RomFfnWeights), P, F32,
+                                              ctypes.c_int, P, I64, P, P, P, P, P, P, SZ, P]
     lib.rom_hybrid_stack_forward.restype = ctypes.c_int
     lib.rom_hybrid_stack_forward.argtypes = [ctypes.POINTER(RomDims), ctypes.c_int32, ctypes.POINTER(_RomBlock),
                                              ctypes.POINTER(_RomFfnWeights), ctypes.c_int, ctypes.c_int, F32, P,
@@ -306,16 +316,27 @@ def rom_block_backward_workspace_bytes(dims: RomDims, B: int, L: int) -> int:
     return int(load_library().rom_block_backward_workspace_bytes(ctypes.byref(dims), B, L))
 
 
-def rom_block_backward(dims, weights, norm_weight, eps, x, B, L, d_out, d_x, grads, d_norm_weight, ws, d_gate_ffn=None):
+def rom_block_forward_train(dims, weights, norm_weight, eps, x, B, L, out, ws):
+    """The training step's forward of a block (plain weights), activations left in ws."""
+    code = load_library().rom_block_forward_train(
+        ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(norm_weight), eps, _ptr(x), B, L, _ptr(out),
+        _ptr(ws), _nbytes(ws), _stream())
+    _check(code, "rom_block_forward_train")
+
+
+def rom_block_backward(dims, weights, norm_weight, eps, x, B, L, d_out, d_x, grads, d_norm_weight, ws, d_gate_ffn=None,
+                       saved=False):
     """weights: the plain ones (w_in not folded); grads as for rom_layer_backward; d_gate_ffn: the gate
-    gradient of an FFN-MoE layer on this block's routing decision (f32 [B*L, K]) or None."""
+    gradient of an FFN-MoE layer on this block's routing decision (f32 [B*L, K]) or None; saved:
+    rom_block_backward_saved (ws holds what rom_block_forward_train has just left)."""
     gs = _RomGrads()
     for name, _ in _RomGrads._fields_:
         setattr(gs, name, _ptr(grads.get(name)))
-    code = load_library().rom_block_backward(
-        ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(norm_weight), eps, _ptr(x), B, L, _ptr(d_out),
-        _ptr(d_gate_ffn), _ptr(d_x), ctypes.byref(gs), _ptr(d_norm_weight), _ptr(ws), _nbytes(ws), _stream())
-    _check(code, "rom_block_backward")
+    lib = load_library()
+    fn = lib.rom_block_backward_saved if saved else lib.rom_block_backward
+    code = fn(ctypes.byref(dims), ctypes.byref(_weights_struct(weights)), _ptr(norm_weight), eps, _ptr(x), B, L, _ptr(d_out),
+              _ptr(d_gate_ffn), _ptr(d_x), ctypes.byref(gs), _ptr(d_norm_weight), _ptr(ws), _nbytes(ws), _stream())
+    _check(code, "rom_block_backward_saved" if saved else "rom_block_backward")
 
 
 def _nbytes(t) -> int:
@@ -702,15 +723,38 @@ class RomLayer:
         rom_layer_backward(self.dims, self.weights, x, B, L, d_out, d_x, grads, self._bwd_ws, saved=saved)
         return d_x, grads
 
-    def block_backward(self, x: torch.Tensor, d_out: torch.Tensor, eps: float = 1e-5, d_gate_ffn=None):
-        """(d_x, grads) of the pre-norm residual block out = x + layer(RMSNorm(x)); grads also holds
-        d_norm_w.  Uses the plain weights (the fold of block_weights() is the forward's business)."""
-        B, L, _ = x.shape
+    def _block_backward_workspace(self, B: int, L: int) -> torch.Tensor:
         need = rom_block_backward_workspace_bytes(self.dims, max(B, 1), max(L, 1))
         if need == 0:
             raise RomError("rom_block_backward_workspace_bytes returned 0: unsupported dims")
         if self._blk_bwd_ws is None or self._blk_bwd_ws.numel() < need:
             self._blk_bwd_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._blk_bwd_ws
+
+    def block_forward_train(self, x: torch.Tensor, eps: float = 1e-5) -> torch.Tensor:
+        """The block's output by rom_block_forward_train (plain weights, activations kept in the block's
+        backward workspace): block_backward(x, d_out, saved=True) then skips the forward recomputation.
+        The routing decision of the call: train_routing_view(name, B, L)."""
+        B, L, _ = x.shape
+        out = torch.empty_like(x)
+        rom_block_forward_train(self.dims, self.weights, self.weights["norm_w"], eps, x, B, L, out,
+                                self._block_backward_workspace(B, L))
+        return out
+
+    def train_routing_view(self, name: str, B: int, L: int) -> torch.Tensor:
+        keep = self._ws
+        self._ws = self._blk_bwd_ws
+        try:
+            return self.ws_view(name, B, L)
+        finally:
+            self._ws = keep
+
+    def block_backward(self, x: torch.Tensor, d_out: torch.Tensor, eps: float = 1e-5, d_gate_ffn=None, saved: bool = False):
+        """(d_x, grads) of the pre-norm residual block out = x + layer(RMSNorm(x)); grads also holds
+        d_norm_w.  Uses the plain weights (the fold of block_weights() is the forward's business).
+        saved: the activations are those block_forward_train(x) has just left."""
+        B, L, _ = x.shape
+        self._block_backward_workspace(B, L)
         d_x = torch.empty_like(x)
         grads = {}
         for name, _ in _RomGrads._fields_:
@@ -719,7 +763,7 @@ class RomLayer:
                 grads[name] = torch.empty(wt.shape, dtype=torch.float32, device=self.device)
         grads["d_norm_w"] = torch.empty(self.dims.d_model, dtype=torch.float32, device=self.device)
         rom_block_backward(self.dims, self.weights, self.weights["norm_w"], eps, x, B, L, d_out, d_x, grads,
-                           grads["d_norm_w"], self._blk_bwd_ws, d_gate_ffn=d_gate_ffn)
+                           grads["d_norm_w"], self._blk_bwd_ws, d_gate_ffn=d_gate_ffn, saved=saved)
         return d_x, grads
 
     def block_backward_xn(self, B: int, L: int) -> torch.Tensor:
@@ -823,14 +867,32 @@ class RomFfnMoe:
                             routing["inv_perm"], routing["gate"], out, self._ws)
         return out
 
-    def backward(self, x: torch.Tensor, routing, d_out: torch.Tensor, pre_norm: bool = False, add_skip: bool = False):
-        """(d_x, d_gate [N, K], {d_w_gate_up (packed row order), d_w_down, d_norm_w}) of forward(x, routing, ...)."""
-        n = x.numel() // self.dims.d_model
+    def _backward_workspace(self, n: int) -> torch.Tensor:
         need = rom_ffn_backward_workspace_bytes(self.dims, self.d_ff, max(n, 1))
         if need == 0:
             raise RomError("rom_ffn_backward_workspace_bytes returned 0: unsupported dims or d_ff")
         if self._bwd_ws is None or self._bwd_ws.numel() < need:
             self._bwd_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._bwd_ws
+
+    def forward_train(self, x: torch.Tensor, routing, pre_norm: bool = False, add_skip: bool = False,
+                      out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """The layer's output by rom_ffn_moe_forward_train (unfolded packed weights, activations kept):
+        backward(..., saved=True) with the same arguments then skips the forward recomputation."""
+        n = x.numel() // self.dims.d_model
+        if out is None:
+            out = torch.empty_like(x)
+        rom_ffn_moe_forward_train(self.dims, self.d_ff, self.packed(False), self.w_down, self.norm_w if pre_norm else None,
+                                  self.eps, add_skip, x, n, routing["offsets"], routing["perm"], routing["inv_perm"],
+                                  routing["gate"], out, self._backward_workspace(n))
+        return out
+
+    def backward(self, x: torch.Tensor, routing, d_out: torch.Tensor, pre_norm: bool = False, add_skip: bool = False,
+                 saved: bool = False):
+        """(d_x, d_gate [N, K], {d_w_gate_up (packed row order), d_w_down, d_norm_w}) of forward(x, routing, ...).
+        saved: the activations are those forward_train(x, routing, ...) has just left."""
+        n = x.numel() // self.dims.d_model
+        self._backward_workspace(n)
         d_x = torch.empty_like(x)
         f32 = dict(dtype=torch.float32, device=self.device)
         d_gate = torch.empty((n, self.dims.top_k), **f32)
@@ -841,7 +903,7 @@ class RomFfnMoe:
         rom_ffn_moe_backward(self.dims, self.d_ff, self.packed(False), self.w_down, self.norm_w if pre_norm else None,
                              self.eps, add_skip, x, n, routing["offsets"], routing["perm"], routing["inv_perm"],
                              routing["gate"], d_out, d_x, d_gate, grads["d_w_gate_up"], grads["d_w_down"],
-                             grads.get("d_norm_w"), self._bwd_ws)
+                             grads.get("d_norm_w"), self._bwd_ws, saved=saved)
         return d_x, d_gate, grads
 
 
@@ -849,16 +911,27 @@ def rom_ffn_backward_workspace_bytes(dims: RomDims, d_ff: int, N: int) -> int:
     return int(load_library().rom_ffn_backward_workspace_bytes(ctypes.byref(dims), d_ff, N))
 
 
+def rom_ffn_moe_forward_train(dims, d_ff, w_gate_up_packed, w_down, norm_weight, eps, add_skip, x, N, offsets, perm,
+                              inv_perm, gate, out, ws):
+    wst = _RomFfnWeights(_ptr(w_gate_up_packed), _ptr(w_down))
+    code = load_library().rom_ffn_moe_forward_train(
+        ctypes.byref(dims), d_ff, ctypes.byref(wst), _ptr(norm_weight), eps, int(bool(add_skip)), _ptr(x), N, _ptr(offsets),
+        _ptr(perm), _ptr(inv_perm), _ptr(gate), _ptr(out), _ptr(ws), _nbytes(ws), _stream())
+    _check(code, "rom_ffn_moe_forward_train")
+
+
 def rom_ffn_moe_backward(dims, d_ff, w_gate_up_packed, w_down, norm_weight, eps, add_skip, x, N, offsets, perm, inv_perm,
-                         gate, d_out, d_x, d_gate, d_w_gate_up, d_w_down, d_norm_weight, ws):
-    """w_gate_up_packed: packed WITHOUT the norm's scale; norm_weight None: no pre-norm."""
+                         gate, d_out, d_x, d_gate, d_w_gate_up, d_w_down, d_norm_weight, ws, saved=False):
+    """w_gate_up_packed: packed WITHOUT the norm's scale; norm_weight None: no pre-norm; saved:
+    rom_ffn_moe_backward_saved (ws holds what rom_ffn_moe_forward_train has just left)."""
     wst = _RomFfnWeights(_ptr(w_gate_up_packed), _ptr(w_down))
     gst = _RomFfnGrads(_ptr(d_w_gate_up), _ptr(d_w_down), _ptr(d_norm_weight))
-    code = load_library().rom_ffn_moe_backward(
+    lib_fn = load_library().rom_ffn_moe_backward_saved if saved else load_library().rom_ffn_moe_backward
+    code = lib_fn(
         ctypes.byref(dims), d_ff, ctypes.byref(wst), _ptr(norm_weight), eps, int(bool(add_skip)), _ptr(x), N, _ptr(offsets),
         _ptr(perm), _ptr(inv_perm), _ptr(gate), _ptr(d_out), _ptr(d_x), _ptr(d_gate), ctypes.byref(gst), _ptr(ws),
         _nbytes(ws), _stream())
-    _check(code, "rom_ffn_moe_backward")
+    _check(code, "rom_ffn_moe_backward_saved" if saved else "rom_ffn_moe_backward")
 
 
 class RomHybridStack:

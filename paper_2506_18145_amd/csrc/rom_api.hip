@@ -954,22 +954,28 @@ size_t rom_ffn_backward_workspace_bytes(const rom_dims *dims, int32_t d_ff, int6
   return make_ffn_bwd_plan(dims, d_ff, N > 0 ? N : 1).total;
 }
 
-int rom_ffn_moe_backward(const rom_dims *dims, int32_t d_ff, const rom_ffn_weights *w, const float *norm_weight, float eps,
-                         int add_skip, const void *x, int64_t N, const int32_t *offsets, const int32_t *perm,
-                         const int32_t *inv_perm, const float *gate, const void *d_out, void *d_x, float *d_gate,
-                         const rom_ffn_grads *gr, void *ws, size_t ws_bytes, void *hip_stream) {
+namespace {
+// what of the FFN-MoE layer's training step a call runs
+enum { kFfnForward = 1, kFfnBackward = 2 };
+int ffn_train_impl(int what, const rom_dims *dims, int32_t d_ff, const rom_ffn_weights *w, const float *norm_weight, float eps,
+                   int add_skip, const void *x, int64_t N, const int32_t *offsets, const int32_t *perm,
+                   const int32_t *inv_perm, const float *gate, void *out, const void *d_out, void *d_x, float *d_gate,
+                   const rom_ffn_grads *gr, void *ws, size_t ws_bytes, void *hip_stream) {
+  const bool fwd = (what & kFfnForward) != 0, bwd = (what & kFfnBackward) != 0;
   int rc = check_ffn(dims, d_ff);
   if (rc != ROM_OK) return rc;
   if (!w || !w->w_gate_up || !w->w_down || !aligned16(w->w_gate_up) || !aligned16(w->w_down)) return ROM_E_INVAL;
   const bool pre_norm = norm_weight != nullptr;
   if (N < 0 || (pre_norm && (!(eps >= 0.0f) || !aligned16(norm_weight)))) return ROM_E_INVAL;
   if (N == 0) return ROM_OK;
-  if (!x || !d_out || !d_x || d_x == x || d_x == d_out || !offsets || !perm || !inv_perm || !gate || !d_gate || !gr || !ws)
+  if (!x || !offsets || !perm || !inv_perm || !gate || !ws || !aligned16(x) ||
+      (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0)
     return ROM_E_INVAL;
-  if (!gr->d_w_gate_up || !gr->d_w_down || !aligned16(gr->d_w_gate_up) || !aligned16(gr->d_w_down) ||
-      (pre_norm && !gr->d_norm_weight))
+  if (!bwd && (!out || out == x || !aligned16(out))) return ROM_E_INVAL;
+  if (bwd && (!d_out || !d_x || d_x == x || d_x == d_out || !d_gate || !gr || !aligned16(d_out) || !aligned16(d_x)))
     return ROM_E_INVAL;
-  if (!aligned16(x) || !aligned16(d_out) || !aligned16(d_x) || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0)
+  if (bwd && (!gr->d_w_gate_up || !gr->d_w_down || !aligned16(gr->d_w_gate_up) || !aligned16(gr->d_w_down) ||
+              (pre_norm && !gr->d_norm_weight)))
     return ROM_E_INVAL;
   if (N * dims->top_k > (1ll << 24) || dims->d_model % 8 != 0) return ROM_E_UNSUPPORTED;
   const FfnBwdPlan p = make_ffn_bwd_plan(dims, d_ff, N);
@@ -982,10 +988,10 @@ int rom_ffn_moe_backward(const rom_dims *dims, int32_t d_ff, const rom_ffn_weigh
   const bool f32 = dt == ROM_DTYPE_F32;
   int32_t *tok_of_pos = reinterpret_cast<int32_t *>(at(p.tok_of_pos));
   float *rstd = reinterpret_cast<float *>(at(p.rstd));
-  ROM_TRY(launch_ffn_prep(dt, perm, K, S, x, Dm, eps, tok_of_pos, nullptr, s));
+  if (fwd) ROM_TRY(launch_ffn_prep(dt, perm, K, S, x, Dm, eps, tok_of_pos, nullptr, s));
   const void *xin = x;
   if (pre_norm) {       // the experts' input, materialised in the activation type
-    ROM_TRY(launch_rmsnorm_forward(dt, x, norm_weight, eps, N, Dm, at(p.xn), rstd, s));
+    if (fwd) ROM_TRY(launch_rmsnorm_forward(dt, x, norm_weight, eps, N, Dm, at(p.xn), rstd, s));
     xin = at(p.xn);
   }
   // plain grouped GEMM over the sorted positions; W_fwd != NULL: contract over W's row index instead
@@ -1017,10 +1023,16 @@ int rom_ffn_moe_backward(const rom_dims *dims, int32_t d_ff, const rom_ffn_weigh
     const int rc_ = (expr);        \
     if (rc_ != ROM_OK) return rc_; \
   } while (0)
-  // forward recomputation: h = W_gu x~ (pre-activations kept this time), a = SiLU(gate) * up, o = W_down a
-  ROM_RC(gemm(xin, Dm, tok_of_pos, N, w->w_gate_up, 2 * d_ff, Dm, at(p.h), nullptr, nullptr, nullptr));
-  ROM_TRY(launch_swiglu(dt, at(p.h), at(p.a), S, d_ff, s));
-  ROM_RC(gemm(at(p.a), d_ff, nullptr, S, w->w_down, Dm, d_ff, at(p.o), nullptr, nullptr, nullptr));
+  // forward (re)computation: h = W_gu x~ (pre-activations kept this time), a = SiLU(gate) * up, o = W_down a
+  if (fwd) {
+    ROM_RC(gemm(xin, Dm, tok_of_pos, N, w->w_gate_up, 2 * d_ff, Dm, at(p.h), nullptr, nullptr, nullptr));
+    ROM_TRY(launch_swiglu(dt, at(p.h), at(p.a), S, d_ff, s));
+    ROM_RC(gemm(at(p.a), d_ff, nullptr, S, w->w_down, Dm, d_ff, at(p.o), nullptr, nullptr, nullptr));
+  }
+  if (!bwd) {           // the training step's forward: the experts' outputs weighted, brought to token order, skip added
+    ROM_TRY(launch_combine(dt, at(p.o), inv_perm, gate, out, N, K, Dm, add_skip ? x : nullptr, s));
+    return ROM_OK;
+  }
   // d gate of a slot: d_out of its token against its expert's output
   ROM_TRY(launch_gate_backward(dt, d_out, at(p.o), inv_perm, K, S, Dm, d_gate, s));
   // gate-weighted d_out per position; d W_down = sum over an expert's positions of (gate d_out)^T a; d a
@@ -1048,6 +1060,32 @@ int rom_ffn_moe_backward(const rom_dims *dims, int32_t d_ff, const rom_ffn_weigh
     ROM_TRY(launch_add(dt, d_xin, d_out, d_x, N * Dm, s));
   }
   return ROM_OK;
+}
+}  // namespace
+
+int rom_ffn_moe_backward(const rom_dims *dims, int32_t d_ff, const rom_ffn_weights *w, const float *norm_weight, float eps,
+                         int add_skip, const void *x, int64_t N, const int32_t *offsets, const int32_t *perm,
+                         const int32_t *inv_perm, const float *gate, const void *d_out, void *d_x, float *d_gate,
+                         const rom_ffn_grads *gr, void *ws, size_t ws_bytes, void *hip_stream) {
+  return ffn_train_impl(kFfnForward | kFfnBackward, dims, d_ff, w, norm_weight, eps, add_skip, x, N, offsets, perm, inv_perm,
+                        gate, nullptr, d_out, d_x, d_gate, gr, ws, ws_bytes, hip_stream);
+}
+
+int rom_ffn_moe_forward_train(const rom_dims *dims, int32_t d_ff, const rom_ffn_weights *w, const float *norm_weight,
+                              float eps, int add_skip, const void *x, int64_t N, const int32_t *offsets,
+                              const int32_t *perm, const int32_t *inv_perm, const float *gate, void *out, void *ws,
+                              size_t ws_bytes, void *hip_stream) {
+  return ffn_train_impl(kFfnForward, dims, d_ff, w, norm_weight, eps, add_skip, x, N, offsets, perm, inv_perm, gate, out,
+                        nullptr, nullptr, nullptr, nullptr, ws, ws_bytes, hip_stream);
+}
+
+int rom_ffn_moe_backward_saved(const rom_dims *dims, int32_t d_ff, const rom_ffn_weights *w, const float *norm_weight,
+                               float eps, int add_skip, const void *x, int64_t N, const int32_t *offsets,
+                               const int32_t *perm, const int32_t *inv_perm, const float *gate, const void *d_out,
+                               void *d_x, float *d_gate, const rom_ffn_grads *gr, void *ws, size_t ws_bytes,
+                               void *hip_stream) {
+  return ffn_train_impl(kFfnBackward, dims, d_ff, w, norm_weight, eps, add_skip, x, N, offsets, perm, inv_perm, gate, nullptr,
+                        d_out, d_x, d_gate, gr, ws, ws_bytes, hip_stream);
 }
 
 int rom_hybrid_stack_forward(const rom_dims *dims, int32_t d_ff, const rom_block *blocks,
@@ -1504,38 +1542,77 @@ size_t rom_block_backward_workspace_bytes(const rom_dims *d, int64_t B, int64_t 
   return make_block_bwd_plan(d, B, L).total;
 }
 
-int rom_block_backward(const rom_dims *d, const rom_weights *w, const float *norm_weight, float eps, const void *x,
-                       int64_t B, int64_t L, const void *d_out, const float *d_gate_ffn, void *d_x, const rom_grads *gr,
-                       float *d_norm_weight, void *ws, size_t ws_bytes, void *hip_stream) {
+namespace {
+// what of the block's training step a call runs
+enum { kBlockForward = 1, kBlockBackward = 2 };
+int block_train_impl(int what, const rom_dims *d, const rom_weights *w, const float *norm_weight, float eps, const void *x,
+                     int64_t B, int64_t L, void *out, const void *d_out, const float *d_gate_ffn, void *d_x,
+                     const rom_grads *gr, float *d_norm_weight, void *ws, size_t ws_bytes, void *hip_stream) {
+  const bool fwd = (what & kBlockForward) != 0, bwd = (what & kBlockBackward) != 0;
   int rc = check_dims(d);
   if (rc != ROM_OK) return rc;
-  if (!norm_weight || !aligned16(norm_weight) || !(eps >= 0.0f) || !d_norm_weight) return ROM_E_INVAL;
+  if (!norm_weight || !aligned16(norm_weight) || !(eps >= 0.0f) || (bwd && !d_norm_weight)) return ROM_E_INVAL;
   if (B < 0 || L < 0) return ROM_E_INVAL;
   if (B == 0 || L == 0) return ROM_OK;
-  if (!x || !d_out || !d_x || !ws || d_x == x || d_x == d_out || !aligned16(x) || !aligned16(d_out) || !aligned16(d_x) ||
-      (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0)
-    return ROM_E_INVAL;
-  if (d->d_model % 4 != 0) return ROM_E_UNSUPPORTED;
+  if (!x || !ws || !aligned16(x) || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return ROM_E_INVAL;
+  if (bwd && (!d_out || !d_x || d_x == x || d_x == d_out || !aligned16(d_out) || !aligned16(d_x))) return ROM_E_INVAL;
+  if (!bwd && (!out || out == x || !aligned16(out))) return ROM_E_INVAL;
+  if (d->d_model % 8 != 0) return ROM_E_UNSUPPORTED;
   const BlockBwdPlan p = make_block_bwd_plan(d, B, L);
   if (ws_bytes < p.total) return ROM_E_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   char *base = static_cast<char *>(ws);
   const int64_t N = B * L;
   float *rstd = reinterpret_cast<float *>(base + p.rstd);
-  // the layer's backward runs on the materialised norm (the forward block never forms it: its in
-  // projection scales rows of x W'^T instead, which differs by the rounding of xn to the type)
-  ROM_TRY(launch_rmsnorm_forward(d->dtype, x, norm_weight, eps, N, d->d_model, base + p.xn, rstd, s));
   // the router reads the raw x and normalises it itself, exactly as in rom_block_forward: the backward
   // differentiates the expert choice the forward made (a router fed the rounded norm could pick
   // another expert for a token whose two best logits are nearly equal)
   BlockOpts opts;
   opts.norm_w = norm_weight;
   opts.eps = eps;
-  rc = backward_impl(d, w, base + p.xn, B, L, d_out, base + p.d_xn, gr, ws, p.inner, hip_stream, true, d_gate_ffn, x, &opts);
+  if (!bwd) {
+    // the training step's forward: the same arithmetic the backward recomputes (materialised norm, plain
+    // weights), activations left in the workspace for rom_block_backward_saved
+    if (B * L * d->top_k > (1ll << 24) || B > 65535) return ROM_E_UNSUPPORTED;
+    rc = check_weights(d, w);
+    if (rc != ROM_OK) return rc;
+    ROM_TRY(launch_rmsnorm_forward(d->dtype, x, norm_weight, eps, N, d->d_model, base + p.xn, rstd, s));
+    char *layer_out = base + make_bwd_plan(d, B, L).fwd_out;
+    rc = forward_impl(d, w, base + p.xn, B, L, nullptr, nullptr, layer_out, nullptr, nullptr, ws, make_plan(d, B, L).total, s,
+                      nullptr, x, &opts);
+    if (rc != ROM_OK) return rc;
+    ROM_TRY(launch_add(d->dtype, x, layer_out, out, N * d->d_model, s));
+    return ROM_OK;
+  }
+  // the layer's backward runs on the materialised norm (the forward block never forms it: its in
+  // projection scales rows of x W'^T instead, which differs by the rounding of xn to the type)
+  if (fwd) ROM_TRY(launch_rmsnorm_forward(d->dtype, x, norm_weight, eps, N, d->d_model, base + p.xn, rstd, s));
+  rc = backward_impl(d, w, base + p.xn, B, L, d_out, base + p.d_xn, gr, ws, p.inner, hip_stream, fwd, d_gate_ffn, x, &opts);
   if (rc != ROM_OK) return rc;
   ROM_TRY(launch_rmsnorm_backward(d->dtype, x, norm_weight, rstd, base + p.d_xn, d_out, N, d->d_model, d_x,
                                   reinterpret_cast<float *>(base + p.part), d_norm_weight, s));
   return ROM_OK;
+}
+}  // namespace
+
+int rom_block_backward(const rom_dims *d, const rom_weights *w, const float *norm_weight, float eps, const void *x,
+                       int64_t B, int64_t L, const void *d_out, const float *d_gate_ffn, void *d_x, const rom_grads *gr,
+                       float *d_norm_weight, void *ws, size_t ws_bytes, void *hip_stream) {
+  return block_train_impl(kBlockForward | kBlockBackward, d, w, norm_weight, eps, x, B, L, nullptr, d_out, d_gate_ffn, d_x, gr,
+                          d_norm_weight, ws, ws_bytes, hip_stream);
+}
+
+int rom_block_forward_train(const rom_dims *d, const rom_weights *w, const float *norm_weight, float eps, const void *x,
+                            int64_t B, int64_t L, void *out, void *ws, size_t ws_bytes, void *hip_stream) {
+  return block_train_impl(kBlockForward, d, w, norm_weight, eps, x, B, L, out, nullptr, nullptr, nullptr, nullptr, nullptr, ws,
+                          ws_bytes, hip_stream);
+}
+
+int rom_block_backward_saved(const rom_dims *d, const rom_weights *w, const float *norm_weight, float eps, const void *x,
+                             int64_t B, int64_t L, const void *d_out, const float *d_gate_ffn, void *d_x,
+                             const rom_grads *gr, float *d_norm_weight, void *ws, size_t ws_bytes, void *hip_stream) {
+  return block_train_impl(kBlockBackward, d, w, norm_weight, eps, x, B, L, nullptr, d_out, d_gate_ffn, d_x, gr, d_norm_weight, ws,
+                          ws_bytes, hip_stream);
 }
 
 namespace {

@@ -128,6 +128,12 @@ int main() {
       CHECK(rom_block_backward(&d, &w, nw, 1e-5f, addr, 1, 8, addr, nullptr, addr, &g, dnw, addr, 4096, nullptr) == ROM_E_INVAL);        // d_x == x
       CHECK(rom_block_backward(&d, &w, nw, 1e-5f, addr, 1, 8, addr, nullptr, addr + 4096, &g, dnw, addr, 4096, nullptr) == ROM_E_WORKSPACE);
       CHECK(rom_block_backward(&d, &w, nw, 1e-5f, addr, 0, 8, addr, nullptr, addr + 4096, &g, dnw, addr, 4096, nullptr) == ROM_OK);
+      CHECK(rom_block_backward_saved(&d, &w, nw, 1e-5f, addr, 1, 8, addr, nullptr, addr + 4096, &g, dnw, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+      CHECK(rom_block_backward_saved(&d, &w, nw, 1e-5f, addr, 1, 8, addr, nullptr, addr, &g, dnw, addr, 4096, nullptr) == ROM_E_INVAL);
+      CHECK(rom_block_forward_train(&d, &w, nw, 1e-5f, addr, 1, 8, addr + 4096, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+      CHECK(rom_block_forward_train(&d, &w, nw, 1e-5f, addr, 1, 8, addr, addr, 4096, nullptr) == ROM_E_INVAL);          // out == x
+      CHECK(rom_block_forward_train(&d, &w, nullptr, 1e-5f, addr, 1, 8, addr + 4096, addr, 4096, nullptr) == ROM_E_INVAL);
+      CHECK(rom_block_forward_train(&d, &w, nw, 1e-5f, addr, 0, 8, addr + 4096, addr, 4096, nullptr) == ROM_OK);
     }
     // workspace too small
     CHECK(rom_layer_forward(&d, &w, addr, 1, 8, nullptr, nullptr, addr + 4096, nullptr, nullptr, addr, 16, nullptr) == ROM_E_WORKSPACE);
@@ -272,6 +278,11 @@ int main() {
     CHECK(rom_ffn_moe_backward(&d, d_ff, &fw, fp, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr, addr + 4096, nullptr, &fg, addr, 4096, nullptr) == ROM_E_INVAL);
     CHECK(rom_ffn_moe_backward(&d, d_ff, &fw, fp, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr, addr + 4096, dg, &fg, addr, 4096, nullptr) == ROM_E_WORKSPACE);
     CHECK(rom_ffn_moe_backward(&d, d_ff, &fw, nullptr, 1e-5f, 0, addr, 0, ip, ip, ip, fp, addr, addr + 4096, dg, &fg, addr, 4096, nullptr) == ROM_OK);
+    CHECK(rom_ffn_moe_backward_saved(&d, d_ff, &fw, fp, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr, addr + 4096, dg, &fg, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+    CHECK(rom_ffn_moe_backward_saved(&d, d_ff, &fw, fp, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr, addr, dg, &fg, addr, 4096, nullptr) == ROM_E_INVAL);
+    CHECK(rom_ffn_moe_forward_train(&d, d_ff, &fw, fp, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr + 4096, addr, 4096, nullptr) == ROM_E_WORKSPACE);
+    CHECK(rom_ffn_moe_forward_train(&d, d_ff, &fw, fp, 1e-5f, 1, addr, 8, ip, ip, ip, fp, addr, addr, 4096, nullptr) == ROM_E_INVAL);    // out == x
+    CHECK(rom_ffn_moe_forward_train(&d, d_ff, &fw, fp, 1e-5f, 1, addr, 0, ip, ip, ip, fp, addr + 4096, addr, 4096, nullptr) == ROM_OK);
   }
 
   // ---- strings and the profiling bookkeeping

@@ -300,3 +300,76 @@ def test_hybrid_pair_backward_chain(kw):
     assert share > 0.1, "the FFN's gate gradient is too small here to test the hand-over"
     bad = {k: v for k, v in errs.items() if not v <= TOL[cfg.dtype]}
     assert not bad, bad
+
+
+@pytest.mark.parametrize("kw", [dict(cfg_id=195), dict(cfg_id=196, top_k=2, gate_mode=1), dict(cfg_id=197, dtype="fp32", seq_len=70),
+                                dict(cfg_id=199, weight_std=0.1),
+                                dict(cfg_id=198, batch=1, seq_len=5000, d_model=512, d_inner=1024, dt_rank=32)])
+def test_block_training_step_halves(kw):
+    """rom_block_forward_train + rom_block_backward_saved: the same gradients as rom_block_backward, bit
+    for bit, and an output that is the block's (against the oracle; against rom_block_forward up to the
+    rounding of the materialised norm)."""
+    cfg = small_cfg(**kw)
+    w, x = make_weights(cfg), make_input(cfg) * np.float32(1.3)
+    x = round_to_bf16(x) if cfg.dtype == "bf16" else x
+    if w["b_router"] is None:
+        w["b_router"] = np.zeros(cfg.n_experts, np.float32)
+    layer = RomLayer(cfg, w)
+    xd, dd = layer.to_device(x), layer.to_device(_d_out(cfg, x.shape))
+    B, L = cfg.batch, cfg.seq_len
+    d_x, grads = layer.block_backward(xd, dd, eps=1e-5)
+    d_x, grads = d_x.clone(), {k: v.clone() for k, v in grads.items()}
+    layer._blk_bwd_ws.fill_(0xA5)                      # nothing may survive from the call above
+    out = layer.block_forward_train(xd, eps=1e-5)
+    idx = to_np(layer.train_routing_view("expert_idx", B, L))
+    d_x2, grads2 = layer.block_backward(xd, dd, eps=1e-5, saved=True)
+    fused = layer.block_forward(xd, eps=1e-5)
+    torch.cuda.synchronize()
+    assert torch.equal(d_x, d_x2)
+    for k in grads:
+        assert torch.equal(grads[k], grads2[k]), k
+    ref = O.rom_block_forward(x, w, cfg.top_k, cfg.gate_mode, 1e-5, expert_idx=idx)
+    tol = TOL[cfg.dtype]
+    got_branch = to_np(out).astype(np.float64) - np.asarray(x, np.float64)
+    ulp = 2.0 ** -8 if cfg.dtype == "bf16" else 2.0 ** -24
+    slack = ulp * np.max(np.abs(ref["out"])) / np.max(np.abs(ref["branch"]))
+    errs = {"out": rel_err(to_np(out), ref["out"]), "branch": max(rel_err(got_branch, ref["branch"]) - slack, 0.0),
+            "vs fused": rel_err(to_np(out), to_np(fused))}
+    print(f"[train halves {cfg.name}] " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    assert all(v <= tol for v in errs.values()), errs
+
+
+@pytest.mark.parametrize("kw,d_ff,pre_norm,add_skip", [
+    (dict(cfg_id=200), 512, True, True),
+    (dict(cfg_id=201, top_k=2, gate_mode=1), 400, True, False),
+    (dict(cfg_id=202, dtype="fp32", seq_len=90), 272, False, True),
+    (dict(cfg_id=203, batch=1, seq_len=5000, d_model=512, d_inner=1024, dt_rank=32), 1024, True, True),
+])
+def test_ffn_training_step_halves(kw, d_ff, pre_norm, add_skip):
+    """rom_ffn_moe_forward_train + rom_ffn_moe_backward_saved: the gradients of rom_ffn_moe_backward bit
+    for bit, and the layer's output (against the oracle and against the fused forward)."""
+    cfg = small_cfg(weight_std=0.08, **kw)
+    w, fw, x = make_weights(cfg), make_ffn_weights(cfg, d_ff), make_input(cfg) * np.float32(1.3)
+    x = round_to_bf16(x) if cfg.dtype == "bf16" else x
+    layer = RomLayer(cfg, w)
+    ffn = RomFfnMoe(layer, d_ff, fw, eps=1e-5)
+    N = cfg.batch * cfg.seq_len
+    xd = layer.to_device(x).view(N, -1)
+    dd = layer.to_device(_d_out(cfg, x.shape)).view(N, -1)
+    routing = layer.route(xd)
+    d_x, d_gate, grads = ffn.backward(xd, routing, dd, pre_norm=pre_norm, add_skip=add_skip)
+    d_x, d_gate, grads = d_x.clone(), d_gate.clone(), {k: v.clone() for k, v in grads.items()}
+    ffn._bwd_ws.fill_(0xA5)
+    out = ffn.forward_train(xd, routing, pre_norm=pre_norm, add_skip=add_skip)
+    d_x2, d_gate2, grads2 = ffn.backward(xd, routing, dd, pre_norm=pre_norm, add_skip=add_skip, saved=True)
+    fused = ffn.forward(xd, routing, pre_norm=pre_norm, add_skip=add_skip)
+    torch.cuda.synchronize()
+    assert torch.equal(d_x, d_x2) and torch.equal(d_gate, d_gate2)
+    for k in grads:
+        assert torch.equal(grads[k], grads2[k]), k
+    idx, gate = to_np(routing["expert_idx"]), to_np(routing["gate"])
+    ref = O.ffn_moe_forward(x.reshape(N, -1), fw["w_gate_up"], fw["w_down"], idx, gate, fw["norm_w"] if pre_norm else None,
+                            1e-5, skip=add_skip)
+    errs = {"out": rel_err(to_np(out), ref), "vs fused": rel_err(to_np(out), to_np(fused))}
+    print(f"[ffn train halves {cfg.name}] " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    assert all(v <= TOL[cfg.dtype] for v in errs.values()), errs
