@@ -562,7 +562,19 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(const T *__restrict__ a, 
   if (r >= n_rows) return;
   const int64_t ra = r / a_div, rb = b_rows ? b_rows[r] : r;
   float acc = 0.0f;
-  for (int c = lane; c < n_cols; c += 64) acc = fmaf(to_f32(a[ra * n_cols + c]), to_f32(b[rb * n_cols + c]), acc);
+  if (n_cols % 8 == 0) {            // rows are 16-byte aligned: eight (bf16) or two times four (fp32) columns per lane and trip
+    for (int c = lane * 8; c < n_cols; c += 512) {
+      float va[8], vb[8];
+      bwd_load4(a + ra * n_cols + c, va);
+      bwd_load4(a + ra * n_cols + c + 4, va + 4);
+      bwd_load4(b + rb * n_cols + c, vb);
+      bwd_load4(b + rb * n_cols + c + 4, vb + 4);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc = fmaf(va[q], vb[q], acc);
+    }
+  } else {
+    for (int c = lane; c < n_cols; c += 64) acc = fmaf(to_f32(a[ra * n_cols + c]), to_f32(b[rb * n_cols + c]), acc);
+  }
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) acc += __shfl_xor(acc, o, 64);
   if (lane == 0) d_gate[r] = acc;
@@ -660,19 +672,23 @@ template <typename T>
 __global__ __launch_bounds__(256) void dx_finish_kernel(const T *__restrict__ dx_in, const float *__restrict__ d_logits,
                                                         const T *__restrict__ w_router, int64_t n_tok, int d_model,
                                                         int n_experts, T *__restrict__ d_x) {
-  const int64_t i = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) * 4;
+  // eight consecutive columns of one token per thread (d_model is a multiple of 8)
+  const int64_t i = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) * 8;
   if (i >= n_tok * d_model) return;
   const int64_t n = i / d_model;
   const int d = static_cast<int>(i % d_model);
-  float v[4], wv[4];
+  float v[8], wv[8];
   bwd_load4(dx_in + i, v);
+  bwd_load4(dx_in + i + 4, v + 4);
   for (int e = 0; e < n_experts; ++e) {
     const float dl = d_logits[n * n_experts + e];
     bwd_load4(w_router + static_cast<int64_t>(e) * d_model + d, wv);
+    bwd_load4(w_router + static_cast<int64_t>(e) * d_model + d + 4, wv + 4);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) v[q] = fmaf(dl, wv[q], v[q]);
+    for (int q = 0; q < 8; ++q) v[q] = fmaf(dl, wv[q], v[q]);
   }
   bwd_store4(d_x + i, v);
+  bwd_store4(d_x + i + 4, v + 4);
 }
 
 // ------------------------------------------------------------------ adjoint of conv + SiLU, Eq. (2)
@@ -1508,7 +1524,7 @@ hipError_t launch_router_backward(int dtype, const float *logits, const int32_t 
 
 hipError_t launch_dx_finish(int dtype, const void *dx_in, const float *d_logits, const void *w_router, int64_t n_tok,
                             int d_model, int n_experts, void *d_x, hipStream_t s) {
-  const dim3 grid = grid1d(n_tok * d_model / 4, 256);      // d_model is a multiple of 8
+  const dim3 grid = grid1d(n_tok * d_model / 8, 256);      // d_model is a multiple of 8
   if (dtype == ROM_DTYPE_BF16)
     hipLaunchKernelGGL((dx_finish_kernel<bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(dx_in), d_logits,
                        static_cast<const bf16_t *>(w_router), n_tok, d_model, n_experts, static_cast<bf16_t *>(d_x));
