@@ -658,11 +658,19 @@ __global__ __launch_bounds__(256) void router_wgrad_finish_kernel(const float *_
                                                                   int d_model, int n_experts,
                                                                   float *__restrict__ d_w_router,
                                                                   float *__restrict__ d_b_router) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= n_experts * (d_model + 1)) return;
+  // (four waves per 64 outputs, as in conv_bwd_finish_kernel)
+  __shared__ float sums[4][64];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int i = blockIdx.x * 64 + lane;
+  const bool live = i < n_experts * (d_model + 1);
+  float acc = 0.0f;
+  if (live)
+    for (int c = q; c < n_chunks; c += 4) acc += partial[static_cast<int64_t>(c) * n_experts * (d_model + 1) + i];
+  sums[q][lane] = acc;
+  __syncthreads();
+  if (q != 0 || !live) return;
+  const float tot = (sums[0][lane] + sums[1][lane]) + (sums[2][lane] + sums[3][lane]);
   const int e = i / (d_model + 1), d = i % (d_model + 1);
-  float tot = 0.0f;
-  for (int c = 0; c < n_chunks; ++c) tot += partial[static_cast<int64_t>(c) * n_experts * (d_model + 1) + i];
   if (d < d_model) d_w_router[e * d_model + d] = tot;
   else if (d_b_router) d_b_router[e] = tot;
 }
@@ -827,11 +835,20 @@ __global__ __launch_bounds__(256) void conv_bwd_kernel(const T *__restrict__ xz,
 __global__ __launch_bounds__(256) void conv_bwd_finish_kernel(const float *__restrict__ partial, int64_t n_parts,
                                                               int d_inner, float *__restrict__ d_conv_w,
                                                               float *__restrict__ d_conv_b) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= 5 * d_inner) return;
-  const int j = i / d_inner, ch = i % d_inner;
-  float tot = 0.0f;
-  for (int64_t p = 0; p < n_parts; ++p) tot += partial[(p * 5 + j) * d_inner + ch];
+  // a block owns 64 outputs; its four waves each add every fourth partial in order, then the four sums
+  // are added in wave order (one thread walking all partials is a chain of dependent memory round trips)
+  __shared__ float sums[4][64];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int i = blockIdx.x * 64 + lane;
+  const bool live = i < 5 * d_inner;
+  const int j = live ? i / d_inner : 0, ch = live ? i % d_inner : 0;
+  float acc = 0.0f;
+  if (live)
+    for (int64_t p = q; p < n_parts; p += 4) acc += partial[(p * 5 + j) * d_inner + ch];
+  sums[q][lane] = acc;
+  __syncthreads();
+  if (q != 0 || !live) return;
+  const float tot = (sums[0][lane] + sums[1][lane]) + (sums[2][lane] + sums[3][lane]);
   if (j < 4) d_conv_w[ch * 4 + j] = tot;
   else if (d_conv_b) d_conv_b[ch] = tot;
 }
@@ -1517,7 +1534,7 @@ hipError_t launch_router_backward(int dtype, const float *logits, const int32_t 
     if (n_experts <= 8) ROM_RW(float, 8); else if (n_experts <= 16) ROM_RW(float, 16); else ROM_RW(float, 64);
   }
 #undef ROM_RW
-  hipLaunchKernelGGL(router_wgrad_finish_kernel, grid1d(static_cast<int64_t>(n_experts) * (d_model + 1), 256), dim3(256), 0,
+  hipLaunchKernelGGL(router_wgrad_finish_kernel, grid1d(static_cast<int64_t>(n_experts) * (d_model + 1), 64), dim3(256), 0,
                      s, partial, n_chunks, d_model, n_experts, d_w_router, d_b_router);
   return hipGetLastError();
 }
@@ -1557,7 +1574,7 @@ hipError_t launch_conv_backward(int dtype, const void *xz, int64_t ld_xz, const 
     if (two) ROM_CONV_BWD(float, 2); else ROM_CONV_BWD(float, 1);
   }
 #undef ROM_CONV_BWD
-  hipLaunchKernelGGL(conv_bwd_finish_kernel, grid1d(5 * d_inner, 256), dim3(256), 0, s, partial, B * n_runs, d_inner,
+  hipLaunchKernelGGL(conv_bwd_finish_kernel, grid1d(5 * d_inner, 64), dim3(256), 0, s, partial, B * n_runs, d_inner,
                      d_conv_w, d_conv_b);
   return hipGetLastError();
 }
