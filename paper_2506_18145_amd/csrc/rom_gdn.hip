@@ -477,6 +477,11 @@ __global__ __launch_bounds__(256, 1) void gdn_kernel(const bf16_t *__restrict__ 
 
 // The state every segment starts from: start[0] = s_in (or 0), start[j + 1]^T = M_j start[j]^T + Z_j^T with the
 // carry pass's arrays as stored (M_j[n][m] = Phi_j[m][n]).  Grid (n_heads, B); a thread owns NS / 4 columns of one row.
+// Workgroup barrier for data that travels through LDS only: __syncthreads() also waits for the wave's
+// outstanding global stores, a memory round trip behind every barrier that follows one (the fold stores a
+// segment's start state right before it parks it)
+__device__ __forceinline__ void fold_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 template <int NS>
 __global__ __launch_bounds__(256) void gdn_fold_kernel(const float *__restrict__ carry_z, const float *__restrict__ carry_m,
                                                        const float *__restrict__ s_in, float *__restrict__ s_start,
@@ -498,16 +503,26 @@ __global__ __launch_bounds__(256) void gdn_fold_kernel(const float *__restrict__
       cur[n][v0 + i] = acc[i];
     }
     if (j == n_seg - 1) break;
-    __syncthreads();
+    fold_barrier();
     const float *mrow = carry_m + unit * static_cast<int64_t>(NS) * NS + static_cast<int64_t>(n) * NS;
 #pragma unroll
     for (int i = 0; i < kCols; ++i) acc[i] = carry_z[unit * s_stride + n * kV + v0 + i];
-    for (int m = 0; m < NS; ++m) {
-      const float a = mrow[m];
+    // (the row of M in batches of 16 values, four 16-byte loads at a time: value by value the loop is a
+    // chain of memory round trips)
+    for (int m0 = 0; m0 < NS; m0 += 16) {
+      float4 a4[4];
 #pragma unroll
-      for (int i = 0; i < kCols; ++i) acc[i] = fmaf(a, cur[m][v0 + i], acc[i]);
+      for (int q = 0; q < 4; ++q) a4[q] = *reinterpret_cast<const float4 *>(mrow + m0 + 4 * q);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float a[4] = {a4[q].x, a4[q].y, a4[q].z, a4[q].w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int i = 0; i < kCols; ++i) acc[i] = fmaf(a[r], cur[m0 + 4 * q + r][v0 + i], acc[i]);
+      }
     }
-    __syncthreads();
+    fold_barrier();
   }
 }
 
