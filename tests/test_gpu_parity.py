@@ -229,6 +229,33 @@ def test_route_entry_point():
         print(f"[route {name}] excluded={n_excl} counts={gpu['counts'].tolist()}", flush=True)
 
 
+@pytest.mark.parametrize("n_tok,n_experts,top_k", [
+    (2049, 8, 1), (4099, 3, 1), (8192, 8, 1), (8193, 9, 1), (16383, 8, 1), (16384, 16, 1), (16385, 8, 1),
+    (32768, 8, 1), (32769, 8, 1), (5000, 16, 3), (16384, 16, 2), (16385, 16, 2), (10923, 6, 3), (40000, 16, 1),
+    (9000, 20, 2),
+])
+def test_grouping_across_slot_counts(n_tok, n_experts, top_k):
+    """The stable grouping at slot counts around the block and wave boundaries of its kernels (ragged
+    last blocks, one slot past a power of two, expert counts that are no power of two), with a skewed
+    assignment that leaves some experts almost or wholly empty: bit-exact against the oracle's stable
+    sort."""
+    cfg = small_cfg(batch=1, seq_len=n_tok, d_model=32, n_experts=n_experts, top_k=top_k, dtype="fp32", cfg_id=70)
+    w = make_weights(cfg)
+    w["b_router"] = np.linspace(-6.0, 2.0, n_experts).astype(np.float32)     # the low experts get next to nothing
+    x = make_input(cfg)
+    from paper_2506_18145_amd import RomLayer
+    layer = RomLayer(cfg, w)
+    res = layer.route(layer.to_device(x).view(-1, cfg.d_model))
+    torch.cuda.synchronize()
+    gpu = {k: to_np(v) for k, v in res.items()}
+    idx = gpu["expert_idx"].astype(np.int32)
+    assert idx.min() >= 0 and idx.max() < n_experts
+    counts, offsets, perm, inv_perm = O.expert_permutation(idx, n_experts)
+    for name, want in (("counts", counts), ("offsets", offsets), ("perm", perm), ("inv_perm", inv_perm)):
+        assert np.array_equal(gpu[name], want), name
+    print(f"[grouping N={n_tok} E={n_experts} K={top_k}] counts={counts.tolist()}", flush=True)
+
+
 def test_route_with_exact_ties_picks_lowest_index():
     cfg = small_cfg(batch=1, seq_len=64, n_experts=8, top_k=2, dtype="fp32")
     w = make_weights(cfg)
