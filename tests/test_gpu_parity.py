@@ -256,6 +256,35 @@ def test_grouping_across_slot_counts(n_tok, n_experts, top_k):
     print(f"[grouping N={n_tok} E={n_experts} K={top_k}] counts={counts.tolist()}", flush=True)
 
 
+@pytest.mark.parametrize("n_tok,d_model,n_experts,top_k,gate_mode,bias", [
+    (8200, 96, 3, 1, 0, False),        # three MFMA steps: the remainder loop alone; ragged last tile
+    (8193, 544, 8, 2, 1, True),        # one batch of 16 steps + one more; one token past a tile
+    (9000, 2048, 8, 1, 0, False),      # the headline's width
+    (12345, 1024, 9, 3, 0, True),      # 16-expert tiles, seven columns unused
+    (16384, 2048, 16, 2, 1, False),    # more than 64 KiB of LDS
+    (8256, 4096, 16, 8, 1, True),      # the largest K; the widest rows the kernel takes with 16 experts
+])
+def test_route_on_the_matrix_pipe(n_tok, d_model, n_experts, top_k, gate_mode, bias):
+    """Launches with more than 8192 bf16 tokens and up to 16 experts compute the logits with MFMA tiles:
+    indices, gates, logits and the grouping against the oracle over widths, expert counts, K, both gate
+    modes, with and without a router bias."""
+    cfg = small_cfg(batch=1, seq_len=n_tok, d_model=d_model, d_inner=128, n_experts=n_experts, top_k=top_k,
+                    gate_mode=gate_mode, dtype="bf16", cfg_id=71)
+    w = make_weights(cfg)
+    if bias:
+        w["b_router"] = (0.3 * np.random.default_rng(3).standard_normal(n_experts)).astype(np.float32)
+    else:
+        w["b_router"] = None
+    x = make_input(cfg)
+    from paper_2506_18145_amd import RomLayer
+    layer = RomLayer(cfg, w)
+    res = layer.route(layer.to_device(x).view(-1, cfg.d_model))
+    torch.cuda.synchronize()
+    gpu = {k: to_np(v) for k, v in res.items()}
+    _, n_excl = check_routing(cfg, gpu, x, w)
+    print(f"[route mfma N={n_tok} d={d_model} E={n_experts} K={top_k}] excluded={n_excl} counts={gpu['counts'].tolist()}", flush=True)
+
+
 def test_route_with_exact_ties_picks_lowest_index():
     cfg = small_cfg(batch=1, seq_len=64, n_experts=8, top_k=2, dtype="fp32")
     w = make_weights(cfg)
