@@ -148,6 +148,30 @@ def test_random_shapes(seed):
         compare_layer(cfg, gpu, x, w, cs, ss)
 
 
+@pytest.mark.parametrize("seed", [31, 32])
+def test_random_shapes_many_tokens(seed):
+    """Seeded random narrow layers over more than 8192 tokens: the launch shapes that only long inputs
+    reach (router on the matrix pipe when d_model is a multiple of 32 and on the vector ALU otherwise,
+    the three-kernel grouping, 256-row GEMM tiles with ragged expert groups), on sizes off every grid."""
+    import random
+    rng = random.Random(seed)
+    for i in range(5):
+        E = rng.choice([2, 3, 5, 8, 8, 12, 16, 33])
+        B = rng.choice([1, 1, 2, 3])
+        L = rng.randint(8193, 20000) // B + 1
+        kw = dict(name=f"random-long-{seed}-{i}", cfg_id=900 + 20 * seed + i, batch=B, seq_len=L,
+                  d_model=rng.choice([32 * rng.randint(1, 12), 8 * rng.randint(4, 48)]), d_inner=16 * rng.randint(2, 16),
+                  d_state=16, d_conv=4, dt_rank=rng.choice([3, 8, 16, 32]), n_experts=E,
+                  top_k=rng.randint(1, min(E, 3)), dtype=rng.choice(["bf16", "bf16", "bf16", "fp32"]),
+                  gate_mode=rng.choice([0, 1]), routed_xdt=rng.choice([True, True, False]))
+        cfg = RomConfig(**kw)
+        cs, ss = make_states(cfg) if rng.choice([False, True]) else (None, None)
+        print(f"[{cfg.name}] B={cfg.batch} L={cfg.seq_len} Dm={cfg.d_model} De={cfg.d_inner} R={cfg.dt_rank} "
+              f"E={E} K={cfg.top_k} {cfg.dtype}", flush=True)
+        _, gpu, x, w = run_layer(cfg, cs, ss)
+        compare_layer(cfg, gpu, x, w, cs, ss)
+
+
 @pytest.mark.parametrize("seed", [21, 22])
 def test_random_shapes_block_and_ffn(seed):
     """The same kind of random shapes through the pre-norm residual block, then an FFN-MoE layer of
