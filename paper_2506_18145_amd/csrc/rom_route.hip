@@ -276,20 +276,30 @@ constexpr int kRouteMfmaBatch = 16;     // fragments of x requested together (16
 constexpr int kRouteMfmaWaves = 4;
 constexpr size_t kRouteMfmaLdsMax = 160 * 1024;
 
-constexpr size_t route_mfma_lds_bytes(int ep, int d_model) {
-  return static_cast<size_t>(ep) * (d_model + 8) * 2 + kRouteMfmaWaves * 16 * 17 * sizeof(float);
+constexpr size_t route_mfma_lds_bytes(int ep, int d_model, bool norm) {
+  return static_cast<size_t>(norm ? 3 : 1) * ep * (d_model + 8) * 2 + kRouteMfmaWaves * 16 * (17 + 1) * sizeof(float);
 }
 
-template <int EP>
+// NORM (the pre-norm block's router): the logits of x * rstd * norm_w.  norm_w is multiplied into the
+// weights while they are copied to LDS, in fp32, and the product is kept as three bf16 pieces (8 + 8 + 8
+// bits of the fp32 significand: the sum of the pieces is the product to within its last bit) in three planes; a step then issues three MFMAs on the same
+// fragment of x - the matrix pipe has the room.  The sum of squares of a token rides along in the
+// vector ALU on the fragments the lanes hold anyway; rstd = 1 / sqrt(mean(x^2) + eps) scales the
+// finished sums and is written out for the in projection's epilogue.
+template <int EP, bool NORM>
 __global__ __launch_bounds__(kRouteMfmaWaves *kWave) void route_mfma_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ w_router, const float *__restrict__ b_router,
     int64_t n_tokens, int d_model, int n_experts, int top_k, int gate_mode,
-    int32_t *__restrict__ expert_idx, float *__restrict__ gate, float *__restrict__ logits) {
+    int32_t *__restrict__ expert_idx, float *__restrict__ gate, float *__restrict__ logits,
+    const float *__restrict__ norm_w, float norm_eps, float *__restrict__ rstd_out) {
   extern __shared__ __attribute__((aligned(16))) unsigned char route_lds[];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int cq = lane & 15, gq = lane >> 4;
   const int pitch = (d_model + 8) * 2;                    // bytes
-  float(*tile)[17] = reinterpret_cast<float(*)[17]>(route_lds + static_cast<size_t>(EP) * pitch) + wave * 16;
+  constexpr int kPlanes = NORM ? 3 : 1;
+  const int plane = EP * pitch;
+  float(*tile)[17] = reinterpret_cast<float(*)[17]>(route_lds + static_cast<size_t>(kPlanes) * plane) + wave * 16;
+  float *rs = reinterpret_cast<float *>(route_lds + static_cast<size_t>(kPlanes) * plane) + kRouteMfmaWaves * 16 * 17 + wave * 16;
 
   {
     const int chunks = d_model / 8;                       // 16-byte pieces per row
@@ -298,7 +308,35 @@ __global__ __launch_bounds__(kRouteMfmaWaves *kWave) void route_mfma_kernel(
       const int n = i / chunks, c = i - n * chunks;
       uint4 v = {0u, 0u, 0u, 0u};
       if (n < n_experts) v = src[static_cast<int64_t>(n) * chunks + c];
-      *reinterpret_cast<uint4 *>(route_lds + n * pitch + c * 16) = v;
+      if (!NORM) {
+        *reinterpret_cast<uint4 *>(route_lds + n * pitch + c * 16) = v;
+      } else {
+        const float4 n0 = *reinterpret_cast<const float4 *>(norm_w + c * 8);
+        const float4 n1 = *reinterpret_cast<const float4 *>(norm_w + c * 8 + 4);
+        const float nw[8] = {n0.x, n0.y, n0.z, n0.w, n1.x, n1.y, n1.z, n1.w};
+        const unsigned int *vw = &v.x;
+        unsigned int hi[4], mid[4], lo[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float f[2] = {__uint_as_float(vw[q] << 16) * nw[2 * q], __uint_as_float(vw[q] & 0xFFFF0000u) * nw[2 * q + 1]};
+          unsigned int piece[3][2];
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const bf16_t a = f32_to_bf16(f[h]);
+            const float r1 = f[h] - bf16_to_f32(a);            // exact: what the first 8 bits leave
+            const bf16_t b = f32_to_bf16(r1);
+            const float r2 = r1 - bf16_to_f32(b);              // exact: what the next 8 bits leave
+            piece[0][h] = a; piece[1][h] = b; piece[2][h] = f32_to_bf16(r2);
+          }
+          hi[q] = piece[0][0] | (piece[0][1] << 16);
+          mid[q] = piece[1][0] | (piece[1][1] << 16);
+          lo[q] = piece[2][0] | (piece[2][1] << 16);
+        }
+        unsigned char *dst = route_lds + n * pitch + c * 16;
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        *reinterpret_cast<uint4 *>(dst + plane) = make_uint4(mid[0], mid[1], mid[2], mid[3]);
+        *reinterpret_cast<uint4 *>(dst + 2 * plane) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+      }
     }
   }
   __syncthreads();
@@ -311,6 +349,23 @@ __global__ __launch_bounds__(kRouteMfmaWaves *kWave) void route_mfma_kernel(
   const int n_steps = d_model / 32;                       // one MFMA each; a step is 4 vectors further along the row
 
   route_f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+  float ss = 0.0f;                                        // NORM: this lane's share of the token's sum of squares
+  auto step = [&](const route_u32x4_t &xv, int ks) {
+#pragma unroll
+    for (int pl = kPlanes - 1; pl >= 0; --pl) {           // smallest pieces first
+      const route_u32x4_t wv = *reinterpret_cast<const route_u32x4_t *>(wp + pl * plane + ks * 64);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(route_bf16x8_t, xv),
+                                                    __builtin_bit_cast(route_bf16x8_t, wv), acc, 0, 0, 0);
+    }
+    if (NORM) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float a = __uint_as_float(xv[q] << 16), b = __uint_as_float(xv[q] & 0xFFFF0000u);
+        ss = fmaf(a, a, ss);
+        ss = fmaf(b, b, ss);
+      }
+    }
+  };
   route_u32x4_t cur[kRouteMfmaBatch], nxt[kRouteMfmaBatch];
   const int n_batches = n_steps / kRouteMfmaBatch;
 #pragma unroll
@@ -324,26 +379,31 @@ __global__ __launch_bounds__(kRouteMfmaWaves *kWave) void route_mfma_kernel(
       for (int u = 0; u < kRouteMfmaBatch; ++u) nxt[u] = __builtin_nontemporal_load(xp + 4 * ((b + 1) * kRouteMfmaBatch + u));
     }
 #pragma unroll
-    for (int u = 0; u < kRouteMfmaBatch; ++u) {
-      const route_u32x4_t wv = *reinterpret_cast<const route_u32x4_t *>(wp + (b * kRouteMfmaBatch + u) * 64);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(route_bf16x8_t, cur[u]),
-                                                    __builtin_bit_cast(route_bf16x8_t, wv), acc, 0, 0, 0);
-    }
+    for (int u = 0; u < kRouteMfmaBatch; ++u) step(cur[u], b * kRouteMfmaBatch + u);
 #pragma unroll
     for (int u = 0; u < kRouteMfmaBatch; ++u) cur[u] = nxt[u];
   }
   for (int ks = n_batches * kRouteMfmaBatch; ks < n_steps; ++ks) {      // d_model / 32 not a multiple of the batch
     const route_u32x4_t xv = xp[4 * ks];
-    const route_u32x4_t wv = *reinterpret_cast<const route_u32x4_t *>(wp + ks * 64);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(route_bf16x8_t, xv),
-                                                  __builtin_bit_cast(route_bf16x8_t, wv), acc, 0, 0, 0);
+    step(xv, ks);
   }
 
+  if (NORM) {
+    // the four lanes of token cq add their shares; the scale goes to the lanes that hold the token's sums
+    ss += __shfl_xor(ss, 16, kWave);
+    ss += __shfl_xor(ss, 32, kWave);
+    const float rstd = 1.0f / sqrtf(ss / static_cast<float>(d_model) + norm_eps);
+    if (gq == 0) {
+      rs[cq] = rstd;
+      if (tok0 + cq < n_tokens) rstd_out[tok0 + cq] = rstd;
+    }
+    __syncthreads();
+  }
   // lane (cq, gq) holds the logits of expert cq for the tokens 4 gq .. 4 gq + 3 of the tile
   const float bias = (b_router && cq < n_experts) ? b_router[cq] : 0.0f;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
-    const float v = acc[r] + bias;
+    const float v = (NORM ? acc[r] * rs[4 * gq + r] : acc[r]) + bias;
     tile[4 * gq + r][cq] = v;
     const int64_t tok = tok0 + 4 * gq + r;
     if (logits && cq < n_experts && tok < n_tokens) logits[tok * n_experts + cq] = v;
@@ -398,7 +458,7 @@ __global__ __launch_bounds__(kRouteMfmaWaves *kWave) void route_mfma_kernel(
 }
 
 // more than 64 KiB of dynamic LDS needs a function attribute, set once per device
-template <int EP> hipError_t route_mfma_allow_lds() {
+template <int EP, bool NORM> hipError_t route_mfma_allow_lds() {
   constexpr int kMaxDevices = 64;
   static std::mutex mu;
   static std::atomic<bool> done[kMaxDevices] = {};
@@ -409,7 +469,7 @@ template <int EP> hipError_t route_mfma_allow_lds() {
   if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
   std::lock_guard<std::mutex> lock(mu);
   if (done[dev].load(std::memory_order_relaxed)) return hipSuccess;
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&route_mfma_kernel<EP>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&route_mfma_kernel<EP, NORM>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kRouteMfmaLdsMax));
   if (e == hipSuccess) done[dev].store(true, std::memory_order_release);
   return e;
@@ -681,23 +741,26 @@ hipError_t route_dispatch(const void *x, const void *w_router, const float *b_ro
                        b_router, n_tokens, d_model, n_experts, top_k, gate_mode, expert_idx,     \
                        gate, logits, norm_w, norm_eps, rstd);                                    \
   } while (0)
-  // bf16, up to 16 experts, no pre-norm: the logits on the matrix pipe
+  // bf16, up to 16 experts: the logits on the matrix pipe (with the pre-norm folded into the weights
+  // three planes of them must fit the LDS)
 #define ROM_ROUTE_LAUNCH_MFMA(EP)                                                                 \
   do {                                                                                           \
-    const size_t lds = route_mfma_lds_bytes(EP, d_model);                                        \
+    const size_t lds = route_mfma_lds_bytes(EP, d_model, NORM);                                  \
     if (lds > 64 * 1024) {                                                                       \
-      const hipError_t e = route_mfma_allow_lds<EP>();                                           \
+      const hipError_t e = route_mfma_allow_lds<EP, NORM>();                                     \
       if (e != hipSuccess) return e;                                                             \
     }                                                                                            \
     const int64_t blocks = ceil_div(n_tokens, 16 * kRouteMfmaWaves);                             \
-    hipLaunchKernelGGL((route_mfma_kernel<EP>), dim3(static_cast<unsigned>(blocks)),             \
+    hipLaunchKernelGGL((route_mfma_kernel<EP, NORM>), dim3(static_cast<unsigned>(blocks)),       \
                        dim3(kRouteMfmaWaves *kWave), lds, s, reinterpret_cast<const bf16_t *>(x), \
                        reinterpret_cast<const bf16_t *>(w_router), b_router, n_tokens, d_model,  \
-                       n_experts, top_k, gate_mode, expert_idx, gate, logits);                   \
+                       n_experts, top_k, gate_mode, expert_idx, gate, logits, norm_w, norm_eps,  \
+                       rstd);                                                                    \
   } while (0)
-  else if (std::is_same<T, bf16_t>::value && !NORM && n_experts <= 16 && d_model % 32 == 0 &&
-           route_mfma_lds_bytes(n_experts <= 8 ? 8 : 16, d_model) <= kRouteMfmaLdsMax &&
-           (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(w_router) & 15) == 0) {
+  else if (std::is_same<T, bf16_t>::value && n_experts <= 16 && d_model % 32 == 0 &&
+           route_mfma_lds_bytes(n_experts <= 8 ? 8 : 16, d_model, NORM) <= kRouteMfmaLdsMax &&
+           (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(w_router) & 15) == 0 &&
+           (!NORM || (reinterpret_cast<uintptr_t>(norm_w) & 15) == 0)) {
     if (n_experts <= 8) ROM_ROUTE_LAUNCH_MFMA(8);
     else ROM_ROUTE_LAUNCH_MFMA(16);
   }
