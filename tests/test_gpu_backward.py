@@ -104,6 +104,29 @@ def test_backward_medium(kw):
     run_backward(small_cfg(**kw))
 
 
+@pytest.mark.parametrize("seed", [6, 8])
+def test_backward_random_long_shapes(seed):
+    """Seeded random narrow layers over more than 8192 tokens (the backward's launch shapes that only
+    long inputs reach: router on the matrix pipe, 256-row tiles with ragged groups, time-chunked adjoint
+    scan), widths on and off the 256 grid of the big weight-gradient kernel, any top-K."""
+    import random
+    rng = random.Random(seed)
+    for i in range(6):
+        E = rng.choice([2, 3, 5, 8, 12, 16])
+        B = rng.choice([1, 1, 2, 3])
+        L = rng.randint(8193, 14000) // B + 1
+        kw = dict(name=f"random-long-bwd-{seed}-{i}", cfg_id=1200 + i, batch=B, seq_len=L,
+                  d_model=rng.choice([32 * rng.randint(2, 10), 8 * rng.randint(8, 40), 256]),
+                  d_inner=rng.choice([16 * rng.randint(2, 16), 256]), d_state=16, d_conv=4,
+                  dt_rank=rng.choice([3, 8, 16, 32]), n_experts=E, top_k=rng.randint(1, min(E, 3)),
+                  dtype=rng.choice(["bf16", "bf16", "fp32"]), gate_mode=rng.choice([0, 1]),
+                  routed_xdt=rng.choice([True, True, False]), weight_std=0.05)
+        cfg = RomConfig(**kw)
+        print(f"[{cfg.name}] B={B} L={L} Dm={cfg.d_model} De={cfg.d_inner} R={cfg.dt_rank} E={E} K={cfg.top_k} "
+              f"{cfg.dtype} gate_mode={cfg.gate_mode} routed_xdt={cfg.routed_xdt}", flush=True)
+        run_backward(cfg)
+
+
 @pytest.mark.parametrize("kw", [dict(), dict(top_k=2, gate_mode=1), dict(dtype="fp32", routed_xdt=False),
                                 dict(batch=1, seq_len=3000, d_model=512, d_inner=1024, dt_rank=64, top_k=2, gate_mode=1,
                                      n_experts=6, cfg_id=163)])
