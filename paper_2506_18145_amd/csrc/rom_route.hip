@@ -301,6 +301,22 @@ __global__ __launch_bounds__(kRouteMfmaWaves *kWave) void route_mfma_kernel(
   float(*tile)[17] = reinterpret_cast<float(*)[17]>(route_lds + static_cast<size_t>(kPlanes) * plane) + wave * 16;
   float *rs = reinterpret_cast<float *>(route_lds + static_cast<size_t>(kPlanes) * plane) + kRouteMfmaWaves * 16 * 17 + wave * 16;
 
+  const int64_t tok0 = (static_cast<int64_t>(blockIdx.x) * kRouteMfmaWaves + wave) * 16;
+  // (a wave past the end walks the last token again and stores nothing: no barrier is skipped)
+  const int64_t tok_ld = (tok0 + cq < n_tokens) ? tok0 + cq : n_tokens - 1;
+  const route_u32x4_t *xp = reinterpret_cast<const route_u32x4_t *>(x + tok_ld * d_model + 8 * gq);
+  const unsigned char *wp = route_lds + (cq % EP) * pitch + 16 * gq;
+  const int n_steps = d_model / 32;                       // one MFMA each; a step is 4 vectors further along the row
+
+  // the first fragments of x are requested before the weights are copied: the copy hides their latency
+  route_u32x4_t cur[kRouteMfmaBatch], nxt[kRouteMfmaBatch];
+  const int n_batches = n_steps / kRouteMfmaBatch;
+#pragma unroll
+  for (int u = 0; u < kRouteMfmaBatch; ++u) {
+    nxt[u] = route_u32x4_t{0u, 0u, 0u, 0u};
+    if (n_batches > 0) cur[u] = __builtin_nontemporal_load(xp + 4 * u);
+  }
+
   {
     const int chunks = d_model / 8;                       // 16-byte pieces per row
     const uint4 *src = reinterpret_cast<const uint4 *>(w_router);
@@ -341,13 +357,6 @@ __global__ __launch_bounds__(kRouteMfmaWaves *kWave) void route_mfma_kernel(
   }
   __syncthreads();
 
-  const int64_t tok0 = (static_cast<int64_t>(blockIdx.x) * kRouteMfmaWaves + wave) * 16;
-  // (a wave past the end walks the last token again and stores nothing: no barrier is skipped)
-  const int64_t tok_ld = (tok0 + cq < n_tokens) ? tok0 + cq : n_tokens - 1;
-  const route_u32x4_t *xp = reinterpret_cast<const route_u32x4_t *>(x + tok_ld * d_model + 8 * gq);
-  const unsigned char *wp = route_lds + (cq % EP) * pitch + 16 * gq;
-  const int n_steps = d_model / 32;                       // one MFMA each; a step is 4 vectors further along the row
-
   route_f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
   float ss = 0.0f;                                        // NORM: this lane's share of the token's sum of squares
   auto step = [&](const route_u32x4_t &xv, int ks) {
@@ -366,13 +375,6 @@ __global__ __launch_bounds__(kRouteMfmaWaves *kWave) void route_mfma_kernel(
       }
     }
   };
-  route_u32x4_t cur[kRouteMfmaBatch], nxt[kRouteMfmaBatch];
-  const int n_batches = n_steps / kRouteMfmaBatch;
-#pragma unroll
-  for (int u = 0; u < kRouteMfmaBatch; ++u) {
-    nxt[u] = route_u32x4_t{0u, 0u, 0u, 0u};
-    if (n_batches > 0) cur[u] = __builtin_nontemporal_load(xp + 4 * u);
-  }
   for (int b = 0; b < n_batches; ++b) {
     if (b + 1 < n_batches) {
 #pragma unroll
