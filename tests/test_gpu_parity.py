@@ -172,6 +172,30 @@ def test_random_shapes_many_tokens(seed):
         compare_layer(cfg, gpu, x, w, cs, ss)
 
 
+@pytest.mark.parametrize("seed", [41, 42])
+def test_random_shapes_many_tokens_block(seed):
+    """The same long narrow random shapes through the pre-norm residual block (router on the normalised
+    input: on the matrix pipe with the norm weight folded into three planes of router weights when
+    d_model is a multiple of 32 and the planes fit the LDS, in the vector ALU otherwise)."""
+    import random
+    rng = random.Random(seed)
+    for i in range(5):
+        E = rng.choice([2, 3, 5, 8, 8, 12, 16, 33])
+        B = rng.choice([1, 1, 2, 3])
+        L = rng.randint(8193, 20000) // B + 1
+        kw = dict(name=f"random-long-block-{seed}-{i}", cfg_id=950 + 20 * (seed - 40) + i, batch=B, seq_len=L,
+                  d_model=rng.choice([32 * rng.randint(1, 12), 8 * rng.randint(4, 48), 2048]), d_inner=16 * rng.randint(2, 16),
+                  d_state=16, d_conv=4, dt_rank=rng.choice([3, 8, 16, 32]), n_experts=E,
+                  top_k=rng.randint(1, min(E, 3)), dtype=rng.choice(["bf16", "bf16", "bf16", "fp32"]),
+                  gate_mode=rng.choice([0, 1]), routed_xdt=rng.choice([True, True, False]), weight_std=0.04)
+        cfg = RomConfig(**kw)
+        cs, ss = make_states(cfg) if rng.choice([False, True]) else (None, None)
+        print(f"[{cfg.name}] B={cfg.batch} L={cfg.seq_len} Dm={cfg.d_model} De={cfg.d_inner} R={cfg.dt_rank} "
+              f"E={E} K={cfg.top_k} {cfg.dtype}", flush=True)
+        _, gpu, x, w = run_layer(cfg, cs, ss, block=True)
+        compare_layer(cfg, gpu, x, w, cs, ss, block=True)
+
+
 @pytest.mark.parametrize("seed", [21, 22])
 def test_random_shapes_block_and_ffn(seed):
     """The same kind of random shapes through the pre-norm residual block, then an FFN-MoE layer of
