@@ -550,7 +550,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_mfma_kernel(const GemmA
 constexpr int kDmaBK = 64, kDmaRC = kDmaBK / 8, kDmaSlots = 5;
 constexpr bool kUseDma = true;
 constexpr int kSkinnyMinWgs = 100;
-constexpr int kSkinnyColsMaxWgs = 200;    // fewer 64 x 128 tiles than this: 64 x 64 tiles instead
+constexpr int kSkinnyColsMaxWgs = 600;    // fewer 64 x 128 tiles than this (about two per CU): 64 x 64 tiles instead
 constexpr bool kUseSmallK = true;
 constexpr int kBigWM = 4, kBigWN = 2;     // wave layout of the 256x256 DMA tile
 
@@ -1002,7 +1002,9 @@ hipError_t launch_mfma_tiles(const GemmArgs &a, hipStream_t s) {
   GemmArgs spread = a;
   spread.no_xcd_remap = 1;
   // a narrow output (the step's out projection: 8 experts x 16 column tiles) leaves half of the CUs
-  // without a workgroup while the weights stream past once: halve the column tile
+  // without a workgroup while the weights stream past once: halve the column tile.  The same helps while
+  // there are only about two workgroups per CU (the step's in projection, 8 x 64 tiles: twice the
+  // workgroups keep more of the weight stream in flight; 256 sequences: step 173 -> 161 us)
   const int64_t row_tiles = (a.n_groups > 0 ? a.n_groups : 1) * ceil_div(rows_per_group > 0 ? rows_per_group : 1, 64);
   if (row_tiles * ceil_div(a.N, 128) < kSkinnyColsMaxWgs && a.N % 64 == 0) return launch_mfma<64, 64, 2, 2, EPI>(spread, s);
   return launch_mfma<64, 128, 2, 2, EPI>(spread, s);
